@@ -1,0 +1,353 @@
+"""Pins for the CPU oracle: it is checked against things other than itself.
+
+The dynamic-programming oracle (oracle/lccrf_oracle.c) is compared with
+  * exhaustive enumeration of all T**L tag paths (the definition: paper Eq. 1-3),
+  * closed forms (zero potentials, position-wise independent potentials, a
+    homogeneous chain through numpy's matrix power, row-stochastic "HMM" potentials,
+    N = 1, T = 1),
+  * the gradient identity p(e) = d logZ / d phi(e) (paper Eq. 4) by central
+    finite differences,
+  * invariants (marginals sum to one, neighbouring edge marginals share their node
+    marginal, shift equivariance, Viterbi score <= logZ <= Viterbi score + L log T),
+  * the entropy identity H = logZ - sum_e p(e) phi(e) (paper Eq. 5-6) against
+    -sum_y p(y) log p(y) from the enumeration.
+A few tests feed the oracle a deliberately wrong input (transposed matrices, a
+shifted position) and check that the pins notice, so that the same slip inside the
+oracle could not pass.
+"""
+import itertools
+import math
+
+import numpy as np
+import pytest
+import scipy.special
+
+from oracle import brute
+from paper_2308_03291_amd import workloads
+
+
+def _rand(seed, B, N, T, scale=1.0):
+    rng = np.random.default_rng(seed)
+    return (rng.standard_normal((B, N, T, T)) * scale).astype(np.float32)
+
+
+BRUTE_SHAPES = [  # (T, N, lengths)
+    (2, 1, [1]), (1, 5, [5, 3]), (2, 6, [6, 1, 0, 4]), (3, 5, [5, 2, 3]), (4, 4, [4, 4]),
+    (5, 8, [8]), (7, 3, [3, 2, 1]), (3, 9, [9, 7]), (6, 6, [6, 5]),
+]
+
+
+@pytest.mark.parametrize("T,N,lens", BRUTE_SHAPES)
+def test_oracle_matches_enumeration(oracle_mod, T, N, lens):
+    B = len(lens)
+    phi = _rand(100 + T * 31 + N, B, N, T, scale=1.5)
+    lengths = np.array(lens, dtype=np.int32)
+    # poison everything the model must not read
+    poisoned = phi.copy()
+    for b, L in enumerate(lens):
+        poisoned[b, L:] = np.nan
+        if L > 0:
+            poisoned[b, 0, 1:] = np.nan
+    logZ, mu = oracle_mod.marginals(poisoned, lengths)
+    score, tags, gap = oracle_mod.viterbi(poisoned, lengths)
+    for b, L in enumerate(lens):
+        r = brute.enumerate_sequence(phi[b].astype(np.float64), L)
+        assert logZ[b] == pytest.approx(r["logZ"], abs=1e-11)
+        assert np.abs(mu[b] - r["mu"]).max() < 1e-12
+        assert score[b] == pytest.approx(r["score"], abs=1e-12)
+        assert list(tags[b]) == list(r["path"])
+        if math.isinf(r["gap"]):
+            assert math.isinf(gap[b]) and gap[b] > 0
+        else:
+            assert gap[b] == pytest.approx(r["gap"], abs=1e-11)
+
+
+def test_config1_all_paths(oracle_mod):
+    """The smallest named workload: 4 sequences, 8 positions, 5 tags, all 5**8 paths each."""
+    w = workloads.WORKLOADS["cfg1"]
+    phi = workloads.phi_batch(w).numpy()
+    lens = workloads.lengths(w).numpy()
+    logZ, mu = oracle_mod.marginals(phi, lens)
+    score, tags, gap = oracle_mod.viterbi(phi, lens)
+    for b in range(w.B):
+        r = brute.enumerate_sequence(phi[b].astype(np.float64), int(lens[b]))
+        assert logZ[b] == pytest.approx(r["logZ"], abs=1e-11)
+        assert np.abs(mu[b] - r["mu"]).max() < 1e-12
+        assert list(tags[b]) == list(r["path"])
+        assert score[b] == pytest.approx(r["score"], abs=1e-12)
+        assert gap[b] == pytest.approx(r["gap"], abs=1e-11)
+
+
+def test_config1_golden_file(oracle_mod):
+    """Stored enumeration results for config 1 (written by tests/golden/make_golden.py,
+    which calls only the brute-force enumerator)."""
+    import json
+    import os
+    path = os.path.join(os.path.dirname(__file__), "golden", "cfg1_enumeration.json")
+    with open(path) as f:
+        g = json.load(f)
+    w = workloads.WORKLOADS["cfg1"]
+    phi = workloads.phi_batch(w)
+    logZ = oracle_mod.log_partition(phi, workloads.lengths(w))
+    score, tags, gap = oracle_mod.viterbi(phi, workloads.lengths(w))
+    assert np.allclose(logZ, g["logZ"], atol=1e-10, rtol=0)
+    assert np.allclose(score, g["score"], atol=1e-10, rtol=0)
+    assert tags.tolist() == g["path"]
+
+
+def test_zero_potentials_closed_form(oracle_mod):
+    """phi = 0: every one of the T**L paths has potential 1, so logZ = L log T and all
+    marginals are uniform."""
+    B, N, T = 5, 40, 7
+    lens = np.array([40, 1, 17, 0, 39], dtype=np.int32)
+    phi = np.zeros((B, N, T, T), dtype=np.float32)
+    logZ, mu = oracle_mod.marginals(phi, lens)
+    assert np.allclose(logZ, lens * math.log(T), atol=1e-10)
+    for b, L in enumerate(lens):
+        if L > 0:
+            assert np.allclose(mu[b, 0, 0], 1.0 / T)
+            assert np.all(mu[b, 0, 1:] == 0)
+        assert np.allclose(mu[b, 1:L], 1.0 / T ** 2)
+        assert np.all(mu[b, L:] == 0)
+    score, tags, gap = oracle_mod.viterbi(phi, lens)
+    assert np.all(score == 0)
+    for b, L in enumerate(lens):   # first-maximum tie-breaking: all tags 0
+        assert np.all(tags[b, :L] == 0) and np.all(tags[b, L:] == -1)
+
+
+def test_position_independent_potentials(oracle_mod):
+    """phi[b,i,s,t] = e[b,i,t]: tags are independent, so logZ = sum_i logsumexp_t e[i],
+    edge marginals are outer products of softmaxes, the best path is the per-position
+    argmax."""
+    rng = np.random.default_rng(7)
+    B, N, T = 3, 33, 11
+    lens = np.array([33, 20, 2], dtype=np.int32)
+    e = (rng.standard_normal((B, N, T)) * 2).astype(np.float32)
+    phi = np.broadcast_to(e[:, :, None, :], (B, N, T, T)).copy()
+    logZ, mu = oracle_mod.marginals(phi, lens)
+    score, tags, _ = oracle_mod.viterbi(phi, lens)
+    e64 = e.astype(np.float64)
+    for b, L in enumerate(lens):
+        assert logZ[b] == pytest.approx(scipy.special.logsumexp(e64[b, :L], axis=1).sum(), abs=1e-10)
+        sm = scipy.special.softmax(e64[b, :L], axis=1)
+        assert np.allclose(mu[b, 0, 0], sm[0], atol=1e-13)
+        for i in range(1, L):
+            assert np.allclose(mu[b, i], np.outer(sm[i - 1], sm[i]), atol=1e-13)
+        assert list(tags[b, :L]) == list(e64[b, :L].argmax(axis=1))
+        assert score[b] == pytest.approx(e64[b, :L].max(axis=1).sum(), abs=1e-10)
+
+
+def test_homogeneous_chain_matrix_power(oracle_mod):
+    """Same matrix A at every position: Z = pi0^T exp(A)^(L-1) 1."""
+    rng = np.random.default_rng(11)
+    T, N = 6, 25
+    A = rng.standard_normal((T, T)).astype(np.float32)
+    first = rng.standard_normal((T,)).astype(np.float32)
+    phi = np.broadcast_to(A, (1, N, T, T)).copy()
+    phi[0, 0, 0] = first
+    for L in (1, 2, 9, 25):
+        logZ = oracle_mod.log_partition(phi, np.array([L], dtype=np.int32))
+        M = np.linalg.matrix_power(np.exp(A.astype(np.float64)), L - 1)
+        Z = np.exp(first.astype(np.float64)) @ M @ np.ones(T)
+        assert logZ[0] == pytest.approx(math.log(Z), abs=1e-10)
+
+
+def test_hmm_parameterisation_sums_to_one(oracle_mod):
+    """Row-stochastic transition matrices and a start distribution: total mass 1, logZ = 0."""
+    rng = np.random.default_rng(13)
+    B, N, T = 2, 50, 9
+    P = rng.random((B, N, T, T)) + 0.05
+    P /= P.sum(axis=3, keepdims=True)
+    phi = np.log(P).astype(np.float32)
+    # rounding to float32 breaks exact stochasticity; renormalise in the rounded domain
+    P32 = np.exp(phi.astype(np.float64))
+    logZ = oracle_mod.log_partition(phi, None)
+    # independent value: push a probability vector through the rounded matrices
+    for b in range(B):
+        v = P32[b, 0, 0].copy()
+        for i in range(1, N):
+            v = v @ P32[b, i]
+        assert logZ[b] == pytest.approx(math.log(v.sum()), abs=1e-10)
+        assert abs(logZ[b]) < 1e-4
+
+
+def test_single_position_and_single_tag(oracle_mod):
+    rng = np.random.default_rng(17)
+    phi = rng.standard_normal((3, 1, 8, 8)).astype(np.float32)
+    logZ, mu = oracle_mod.marginals(phi, None)
+    for b in range(3):
+        assert logZ[b] == pytest.approx(scipy.special.logsumexp(phi[b, 0, 0].astype(np.float64)), abs=1e-12)
+        assert np.allclose(mu[b, 0, 0], scipy.special.softmax(phi[b, 0, 0].astype(np.float64)), atol=1e-14)
+    phi1 = rng.standard_normal((2, 12, 1, 1)).astype(np.float32)
+    lens = np.array([12, 5], dtype=np.int32)
+    logZ, mu = oracle_mod.marginals(phi1, lens)
+    for b, L in enumerate(lens):   # one path only
+        assert logZ[b] == pytest.approx(phi1[b, :L, 0, 0].astype(np.float64).sum(), abs=1e-12)
+        assert np.allclose(mu[b, :L, 0, 0], 1.0)
+    score, tags, gap = oracle_mod.viterbi(phi1, lens)
+    assert np.all(np.isposinf(gap))
+    assert np.allclose(score, logZ)
+
+
+def test_marginals_are_the_gradient_of_logZ(oracle_mod):
+    """Paper Eq. 4, with phi holding LOG-potentials: central differences of logZ."""
+    rng = np.random.default_rng(19)
+    B, N, T = 1, 6, 4
+    L = 5
+    lens = np.array([L], dtype=np.int32)
+    # use values exactly representable in float32 after +-h: work on a 2^-10 grid
+    phi = np.round(rng.standard_normal((B, N, T, T)) * 512) / 512
+    phi = phi.astype(np.float32)
+    _, mu = oracle_mod.marginals(phi, lens)
+    h = 2.0 ** -10
+    for (i, s, t) in itertools.product(range(N), range(T), range(T)):
+        p = phi.copy(); p[0, i, s, t] += h
+        m = phi.copy(); m[0, i, s, t] -= h
+        g = (oracle_mod.log_partition(p, lens)[0] - oracle_mod.log_partition(m, lens)[0]) / (2 * h)
+        assert g == pytest.approx(mu[0, i, s, t], abs=2e-7), (i, s, t)
+
+
+@pytest.mark.parametrize("key", ["cfg2", "cfg3"])
+def test_invariants_on_named_workloads(oracle_mod, key):
+    """Sum-to-one, node agreement, zeros outside the chain, bounds; on a slice of the
+    ragged workloads at their real T and N."""
+    w = workloads.WORKLOADS[key]
+    lens_all = workloads.lengths(w)
+    assert int(lens_all.min()) >= w.len_lo and int(lens_all.max()) <= w.len_hi
+    pick = [0, 1, int(lens_all.argmin()), int(lens_all.argmax())]
+    trans = workloads.shared_transitions(w)
+    phi = np.stack([workloads.phi_sequence(w, b, trans).numpy() for b in pick])
+    lens = lens_all[pick].numpy()
+    logZ, mu = oracle_mod.marginals(phi, lens)
+    score, tags, gap = oracle_mod.viterbi(phi, lens)
+    for k, L in enumerate(lens):
+        assert np.allclose(mu[k, :L].sum(axis=(1, 2)), 1.0, atol=1e-12)
+        assert np.all(mu[k, L:] == 0) and np.all(mu[k, 0, 1:] == 0)
+        node_as_target = mu[k, :L].sum(axis=1)        # [L, T]: p(y_i = t)
+        node_as_source = mu[k, 1:L].sum(axis=2)       # [L-1, T]: p(y_{i-1} = s)
+        assert np.allclose(node_as_target[:-1], node_as_source, atol=1e-12)
+        assert score[k] <= logZ[k] <= score[k] + L * math.log(w.T)
+        # the returned path really has the returned score
+        y = tags[k, :L]
+        s = float(phi[k, 0, 0, y[0]]) + sum(float(phi[k, i, y[i - 1], y[i]]) for i in range(1, L))
+        assert s == pytest.approx(score[k], abs=1e-9)
+        assert np.all(tags[k, L:] == -1) and np.all((y >= 0) & (y < w.T))
+        assert gap[k] >= 0
+
+
+def test_shift_equivariance(oracle_mod):
+    """Adding c to one in-chain matrix adds c to logZ and leaves marginals unchanged."""
+    phi = _rand(23, 2, 10, 5)
+    lens = np.array([10, 6], dtype=np.int32)
+    logZ0, mu0 = oracle_mod.marginals(phi, lens)
+    phi2 = phi.copy()
+    phi2[:, 3] += np.float32(1.5)
+    phi2[:, 8] += np.float32(-0.25)   # position 8 is outside sequence 1
+    logZ1, mu1 = oracle_mod.marginals(phi2, lens)
+    assert logZ1[0] == pytest.approx(logZ0[0] + 1.25, abs=1e-6)
+    assert logZ1[1] == pytest.approx(logZ0[1] + 1.5, abs=1e-6)
+    assert np.abs(mu1 - mu0).max() < 1e-6
+
+
+def test_entropy_identity(oracle_mod):
+    """H(p) = logZ - sum_e p(e) phi(e) (paper Eq. 5-6) equals -sum_y p(y) log p(y)."""
+    phi = _rand(29, 3, 7, 3, scale=2.0)
+    lens = np.array([7, 4, 1], dtype=np.int32)
+    logZ, mu = oracle_mod.marginals(phi, lens)
+    for b, L in enumerate(lens):
+        r = brute.enumerate_sequence(phi[b].astype(np.float64), int(L))
+        H = logZ[b] - (mu[b] * np.where(mu[b] > 0, phi[b].astype(np.float64), 0.0)).sum()
+        assert H == pytest.approx(r["entropy"], abs=1e-10)
+        assert -1e-12 <= H <= L * math.log(3) + 1e-12
+
+
+def test_banned_transitions(oracle_mod):
+    """-inf log-potentials forbid an edge: its marginal is 0 and nothing turns NaN."""
+    phi = _rand(31, 2, 5, 3)
+    phi[0, 2, 1, :] = -np.inf      # tag 1 at position 1 has no successor
+    phi[0, 3, :, 0] = -np.inf      # tag 0 at position 3 is unreachable
+    phi[1, 0, 0, 2] = -np.inf      # sequence 1 cannot start in tag 2
+    lens = np.array([5, 4], dtype=np.int32)
+    logZ, mu = oracle_mod.marginals(phi, lens)
+    score, tags, gap = oracle_mod.viterbi(phi, lens)
+    assert np.all(np.isfinite(mu)) and np.all(np.isfinite(logZ))
+    for b, L in enumerate(lens):
+        r = brute.enumerate_sequence(phi[b].astype(np.float64), int(L))
+        assert logZ[b] == pytest.approx(r["logZ"], abs=1e-11)
+        assert np.abs(mu[b] - r["mu"]).max() < 1e-12
+        assert list(tags[b]) == list(r["path"])
+        assert gap[b] == pytest.approx(r["gap"], abs=1e-11)
+    # no finite path at all
+    phi[1, 1, :, :] = -np.inf
+    logZ, mu = oracle_mod.marginals(phi, lens)
+    assert np.isneginf(logZ[1]) and np.all(mu[1] == 0)
+
+
+def test_peaked_potentials_approach_the_best_path(oracle_mod):
+    """Scaling phi by k -> infinity concentrates the distribution on the Viterbi path."""
+    phi = _rand(37, 1, 12, 4)
+    score, tags, gap = oracle_mod.viterbi(phi, None)
+    assert gap[0] > 1e-3
+    big = (phi.astype(np.float64) * 4096).astype(np.float32)
+    _, mu = oracle_mod.marginals(big, None)
+    y = tags[0]
+    assert mu[0, 0, 0, y[0]] > 1 - 1e-9
+    for i in range(1, 12):
+        assert mu[0, i, y[i - 1], y[i]] > 1 - 1e-9
+
+
+def test_bf16_storage_is_widened_exactly(oracle_mod):
+    import torch
+    w = workloads.WORKLOADS["cfg5"]
+    phi_bf = workloads.phi_sequence(w, 1)[:64].unsqueeze(0)            # [1, 64, 16, 16] bf16
+    phi_f = phi_bf.to(torch.float32)
+    a = oracle_mod.marginals(phi_bf, None)
+    b = oracle_mod.marginals(phi_f, None)
+    assert np.array_equal(a[0], b[0]) and np.array_equal(a[1], b[1])
+    assert float(phi_f.abs().max()) > 20   # the x10 scale is really there
+
+
+def test_long_peaked_chain_is_stable(oracle_mod):
+    """Config-5-like values over 4096 positions: finite, normalised, bounded."""
+    w = workloads.WORKLOADS["cfg5"]
+    phi = workloads.phi_sequence(w, 0)[:4096].unsqueeze(0)
+    logZ, mu = oracle_mod.marginals(phi, None)
+    score, _, _ = oracle_mod.viterbi(phi, None, with_gap=False)
+    assert np.isfinite(logZ[0])
+    assert np.allclose(mu[0].sum(axis=(1, 2)), 1.0, atol=1e-9)
+    assert score[0] <= logZ[0] <= score[0] + 4096 * math.log(16)
+
+
+# ---- the pins notice planted mistakes -------------------------------------------------
+
+def test_pins_notice_a_transposed_matrix(oracle_mod):
+    phi = _rand(41, 1, 5, 3, scale=1.5)
+    wrong = np.ascontiguousarray(np.swapaxes(phi, 2, 3))
+    wrong[:, 0] = phi[:, 0]
+    r = brute.enumerate_sequence(phi[0].astype(np.float64), 5)
+    logZ, mu = oracle_mod.marginals(wrong, None)
+    assert abs(logZ[0] - r["logZ"]) > 1e-3
+    assert np.abs(mu[0] - r["mu"]).max() > 1e-3
+
+
+def test_pins_notice_using_all_rows_of_the_first_matrix(oracle_mod):
+    """A reading with a summed-out virtual start tag would give (N+1) log T at phi = 0."""
+    T, N = 4, 6
+    phi = np.zeros((1, N, T, T), dtype=np.float32)
+    logZ = oracle_mod.log_partition(phi, None)
+    assert logZ[0] == pytest.approx(N * math.log(T), abs=1e-12)
+    assert abs(logZ[0] - (N + 1) * math.log(T)) > 1.0
+
+
+def test_workload_generators_are_reproducible():
+    w = workloads.WORKLOADS["cfg3"]
+    a = workloads.phi_sequence(w, 5)
+    b = workloads.phi_sequence(w, 5)
+    assert a.shape == (w.N, w.T, w.T) and np.array_equal(a.numpy(), b.numpy())
+    trans = workloads.shared_transitions(w)
+    # tagging structure: differences between rows do not depend on the position
+    d = (a[:, 1, :] - a[:, 0, :]).numpy()
+    assert np.allclose(d, (trans[1] - trans[0]).numpy()[None, :], atol=1e-5)
+    lens = workloads.lengths(w)
+    assert lens.dtype.is_floating_point is False and lens.shape == (w.B,)
+    assert 1.5 < float(a.std()) < 3.0
