@@ -1,0 +1,138 @@
+/*
+ * lccrf.h - C ABI of the MI355X (gfx950) batched linear-chain CRF library.
+ *
+ * The model is the linear-chain CRF of the paper's section "Sequence Tagging": a
+ * tag path y_0..y_{L-1} over T tags has log-potential
+ *
+ *     score(y) = phi[b][0][0][y_0] + sum_{i=1}^{L-1} phi[b][i][y_{i-1}][y_i]
+ *
+ * with a separate T x T matrix of log-potentials for every position (the paper's
+ * per-time-step transition matrices), p(y) = exp(score(y) - logZ) (section
+ * "Structured Distributions", Eq. 1-2).
+ *
+ * Conventions shared by every entry point
+ * ---------------------------------------
+ *  - All data pointers are DEVICE pointers owned by the caller; the library never
+ *    allocates, frees, synchronises or copies to the host.  Work is enqueued on
+ *    `stream` (a hipStream_t passed as void*; NULL = the default stream) and the
+ *    call returns at once.
+ *  - phi: dense, contiguous, row-major [B][N][T][T], t fastest; element type by
+ *    `dt` (LCCRF_F32: IEEE float; LCCRF_BF16: bfloat16, widened exactly to float
+ *    before use).  s (third index) is the tag at position i-1, t the tag at
+ *    position i.  Of the first matrix only row s = 0 is used: phi[b][0][0][t]
+ *    scores starting in tag t.  Base address 16-byte aligned.
+ *  - lengths: int32 [B] or NULL (= all N).  Values are clamped on the device to
+ *    [0, N].  Positions i >= lengths[b] are never read.  lengths[b] = 0 is the empty
+ *    chain: logZ = 0, marginals 0, score 0, tags -1.
+ *  - -inf potentials are allowed (a forbidden edge; its marginal is 0).  If no path
+ *    has a finite score, logZ = -inf and all marginals are 0.  +inf and NaN inputs
+ *    are undefined.
+ *  - workspace: device scratch of at least lccrf_workspace_bytes(op, ...) bytes,
+ *    256-byte aligned, not shared by calls that may overlap in time.  Contents on
+ *    entry are irrelevant; contents on exit are unspecified.
+ *  - 1 <= T <= LCCRF_MAX_T, B >= 1, N >= 1, B*N*T*T < 2^62.
+ *  - Return value: LCCRF_OK (0) or a negative lccrf_status.  When an error is
+ *    returned nothing has been enqueued.
+ *  - Thread safety: entry points keep no mutable global state; concurrent calls
+ *    with distinct workspaces are safe.
+ */
+#ifndef LCCRF_H
+#define LCCRF_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define LCCRF_MAX_T 256
+
+typedef enum { LCCRF_F32 = 0, LCCRF_BF16 = 1 } lccrf_dtype;
+
+typedef enum { LCCRF_OP_LOGZ = 0, LCCRF_OP_MARGINALS = 1, LCCRF_OP_ARGMAX = 2 } lccrf_op;
+
+/* How the recursion over positions is scheduled.  Results are the same up to
+ * rounding; AUTO picks by shape. */
+typedef enum {
+    LCCRF_ALGO_AUTO = 0,
+    LCCRF_ALGO_SEQUENTIAL = 1, /* position by position (the forward algorithm as the paper uses it) */
+    LCCRF_ALGO_SCAN = 2        /* chunked associative scan over positions (the parallel variant the
+                                  paper cites in "Sequence Tagging"); only where implemented */
+} lccrf_algo;
+
+typedef enum {
+    LCCRF_OK = 0,
+    LCCRF_EINVAL = -1,     /* bad B, N, T, dtype, op or algo */
+    LCCRF_ENULL = -2,      /* a required pointer is NULL */
+    LCCRF_EWORKSPACE = -3, /* workspace NULL or smaller than lccrf_workspace_bytes */
+    LCCRF_EALIGN = -4,     /* phi, an output or the workspace is misaligned */
+    LCCRF_ELAUNCH = -5,    /* the HIP runtime refused a launch */
+    LCCRF_ENOTIMPL = -6    /* the requested algo does not exist for this shape */
+} lccrf_status;
+
+/* Bytes of device scratch the given query needs (a multiple of 256); 0 on invalid
+ * arguments.  Valid for every lccrf_algo. */
+size_t lccrf_workspace_bytes(lccrf_op op, int B, int N, int T, lccrf_dtype dt);
+
+/*
+ * Log-partition function (paper: section "Computing Probability of a Structure and
+ * Partition Function"; forward algorithm of section "Sequence Tagging", O(T^2 N)):
+ *     logZ[b] = log sum_y exp(score_b(y)),   float [B] on the device.
+ */
+int lccrf_log_partition(const void* phi, lccrf_dtype dt, const int32_t* lengths,
+                        int B, int N, int T,
+                        float* logZ,
+                        void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Edge marginals (paper: section "Computing Marginals", Eq. 3 and Eq. 4: the
+ * marginal of a part is the derivative of logZ with respect to its log-potential;
+ * here computed by the hand-written forward-backward recursions):
+ *     marginals[b][i][s][t] = p(y_{i-1} = s, y_i = t)        for 1 <= i < lengths[b]
+ *     marginals[b][0][0][t] = p(y_0 = t)
+ *     0 everywhere else (rows s > 0 of position 0, positions >= lengths[b]).
+ * marginals: float [B][N][T][T], fully written.  logZ: float [B] or NULL.
+ */
+int lccrf_marginals(const void* phi, lccrf_dtype dt, const int32_t* lengths,
+                    int B, int N, int T,
+                    float* logZ, float* marginals,
+                    void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Most probable tag path (paper: section "Computing Most Probable Structure": the
+ * same recursion in the max-plus semiring; the path is what the gradient of the best
+ * score with respect to the potentials marks):
+ *     tags[b][i] in [0, T) for i < lengths[b], -1 for i >= lengths[b]; int32 [B][N].
+ *     best_score[b] = score_b(tags[b]); float [B] or NULL.
+ * Scores are accumulated in double precision.  Among exactly tied paths the one
+ * returned takes the smallest previous tag at every step back from the smallest best
+ * final tag.
+ */
+int lccrf_argmax(const void* phi, lccrf_dtype dt, const int32_t* lengths,
+                 int B, int N, int T,
+                 float* best_score, int32_t* tags,
+                 void* workspace, size_t workspace_bytes, void* stream);
+
+/* The same three queries with the schedule chosen by the caller (tests, benchmarks).
+ * LCCRF_ENOTIMPL if `algo` is not available for the shape. */
+int lccrf_log_partition_algo(const void* phi, lccrf_dtype dt, const int32_t* lengths,
+                             int B, int N, int T, float* logZ,
+                             void* workspace, size_t workspace_bytes, void* stream, lccrf_algo algo);
+int lccrf_marginals_algo(const void* phi, lccrf_dtype dt, const int32_t* lengths,
+                         int B, int N, int T, float* logZ, float* marginals,
+                         void* workspace, size_t workspace_bytes, void* stream, lccrf_algo algo);
+int lccrf_argmax_algo(const void* phi, lccrf_dtype dt, const int32_t* lengths,
+                      int B, int N, int T, float* best_score, int32_t* tags,
+                      void* workspace, size_t workspace_bytes, void* stream, lccrf_algo algo);
+
+/* Static, human-readable text for a status code. */
+const char* lccrf_strerror(int code);
+
+/* Library version: major * 10000 + minor * 100 + patch. */
+int lccrf_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LCCRF_H */

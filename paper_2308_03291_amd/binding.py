@@ -1,0 +1,178 @@
+"""ctypes binding of ``liblccrf.so`` for torch device tensors.
+
+Argument marshalling only: shapes, dtypes and devices are checked, pointers and the current
+HIP stream are handed to the C ABI declared in ``include/lccrf.h``, and every step of the
+computation runs in the library's kernels.  There is no fallback: if the shared library is
+missing or an entry point reports an error, an exception is raised.
+
+The three queries mirror the C entry points:
+  ``lccrf_log_partition``  log-partition function      (paper, "Computing Probability of a
+                           Structure and Partition Function"; forward algorithm of "Sequence Tagging")
+  ``lccrf_marginals``      edge marginals = d logZ / d phi   (paper, "Computing Marginals", Eq. 3-4)
+  ``lccrf_argmax``         most probable tag path, max-plus  (paper, "Computing Most Probable Structure")
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Tuple
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "liblccrf.so")
+
+LCCRF_F32, LCCRF_BF16 = 0, 1
+OP_LOGZ, OP_MARGINALS, OP_ARGMAX = 0, 1, 2
+ALGO_AUTO, ALGO_SEQUENTIAL, ALGO_SCAN = 0, 1, 2
+MAX_T = 256
+
+EXPORTS = (
+    "lccrf_workspace_bytes", "lccrf_log_partition", "lccrf_marginals", "lccrf_argmax",
+    "lccrf_log_partition_algo", "lccrf_marginals_algo", "lccrf_argmax_algo",
+    "lccrf_strerror", "lccrf_version",
+)
+
+_lib = None
+
+
+class LccrfError(RuntimeError):
+    pass
+
+
+def load_library() -> ctypes.CDLL:
+    """Load ``liblccrf.so`` (built by ``build_ext.py``); raises if it is not there."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise LccrfError(
+            f"{LIB_PATH} is missing: build it with `python -m paper_2308_03291_amd.build_ext` "
+            "(or __graft_entry__.build()); there is no fallback path")
+    lib = ctypes.CDLL(LIB_PATH)
+    vp, i, sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_size_t
+    lib.lccrf_workspace_bytes.argtypes = [i, i, i, i, i]
+    lib.lccrf_workspace_bytes.restype = sz
+    base = [vp, i, vp, i, i, i]
+    lib.lccrf_log_partition.argtypes = base + [vp, vp, sz, vp]
+    lib.lccrf_marginals.argtypes = base + [vp, vp, vp, sz, vp]
+    lib.lccrf_argmax.argtypes = base + [vp, vp, vp, sz, vp]
+    lib.lccrf_log_partition_algo.argtypes = base + [vp, vp, sz, vp, i]
+    lib.lccrf_marginals_algo.argtypes = base + [vp, vp, vp, sz, vp, i]
+    lib.lccrf_argmax_algo.argtypes = base + [vp, vp, vp, sz, vp, i]
+    for n in ("lccrf_log_partition", "lccrf_marginals", "lccrf_argmax",
+              "lccrf_log_partition_algo", "lccrf_marginals_algo", "lccrf_argmax_algo", "lccrf_version"):
+        getattr(lib, n).restype = i
+    lib.lccrf_strerror.argtypes = [i]
+    lib.lccrf_strerror.restype = ctypes.c_char_p
+    lib.lccrf_version.argtypes = []
+    _lib = lib
+    return lib
+
+
+def strerror(code: int) -> str:
+    return load_library().lccrf_strerror(int(code)).decode()
+
+
+def _check(rc: int, what: str):
+    if rc != 0:
+        raise LccrfError(f"{what} failed: {strerror(rc)} (status {rc})")
+
+
+def _phi_args(phi: torch.Tensor) -> Tuple[int, int, int, int]:
+    if phi.dim() != 4 or phi.shape[2] != phi.shape[3]:
+        raise ValueError(f"phi must be [B, N, T, T], got {tuple(phi.shape)}")
+    if not phi.is_cuda:
+        raise ValueError("phi must live on the GPU")
+    if not phi.is_contiguous():
+        raise ValueError("phi must be contiguous")
+    if phi.dtype == torch.float32:
+        dt = LCCRF_F32
+    elif phi.dtype == torch.bfloat16:
+        dt = LCCRF_BF16
+    else:
+        raise ValueError(f"phi must be float32 or bfloat16, got {phi.dtype}")
+    B, N, T, _ = phi.shape
+    return dt, int(B), int(N), int(T)
+
+
+def _len_ptr(lengths: Optional[torch.Tensor], B: int, device) -> Optional[int]:
+    if lengths is None:
+        return None
+    if lengths.dtype != torch.int32 or lengths.shape != (B,) or lengths.device != device \
+            or not lengths.is_contiguous():
+        raise ValueError("lengths must be a contiguous int32 [B] tensor on phi's device")
+    return lengths.data_ptr()
+
+
+def _stream(device) -> int:
+    return torch.cuda.current_stream(device).cuda_stream
+
+
+def workspace_bytes(op: int, B: int, N: int, T: int, dtype: int) -> int:
+    return int(load_library().lccrf_workspace_bytes(op, B, N, T, dtype))
+
+
+def _workspace(op: int, B: int, N: int, T: int, dt: int, device, workspace: Optional[torch.Tensor]):
+    need = workspace_bytes(op, B, N, T, dt)
+    if need == 0:
+        raise LccrfError(f"unsupported shape B={B} N={N} T={T} (1 <= T <= {MAX_T})")
+    if workspace is None:
+        workspace = torch.empty(need, dtype=torch.uint8, device=device)
+    elif workspace.dtype != torch.uint8 or workspace.device != device or not workspace.is_contiguous():
+        raise ValueError("workspace must be a contiguous uint8 tensor on phi's device")
+    return workspace, workspace.numel()
+
+
+def lccrf_log_partition(phi: torch.Tensor, lengths: Optional[torch.Tensor] = None, *,
+                        out: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None,
+                        algo: int = ALGO_AUTO) -> torch.Tensor:
+    """logZ [B] float32 on phi's device."""
+    lib = load_library()
+    dt, B, N, T = _phi_args(phi)
+    ws, nws = _workspace(OP_LOGZ, B, N, T, dt, phi.device, workspace)
+    if out is None:
+        out = torch.empty(B, dtype=torch.float32, device=phi.device)
+    with torch.cuda.device(phi.device):
+        rc = lib.lccrf_log_partition_algo(phi.data_ptr(), dt, _len_ptr(lengths, B, phi.device), B, N, T,
+                                          out.data_ptr(), ws.data_ptr(), nws, _stream(phi.device), algo)
+    _check(rc, "lccrf_log_partition")
+    return out
+
+
+def lccrf_marginals(phi: torch.Tensor, lengths: Optional[torch.Tensor] = None, *,
+                    out: Optional[torch.Tensor] = None, logZ: Optional[torch.Tensor] = None,
+                    workspace: Optional[torch.Tensor] = None, algo: int = ALGO_AUTO):
+    """(logZ [B], marginals [B, N, T, T]) float32 on phi's device."""
+    lib = load_library()
+    dt, B, N, T = _phi_args(phi)
+    ws, nws = _workspace(OP_MARGINALS, B, N, T, dt, phi.device, workspace)
+    if out is None:
+        out = torch.empty(B, N, T, T, dtype=torch.float32, device=phi.device)
+    if logZ is None:
+        logZ = torch.empty(B, dtype=torch.float32, device=phi.device)
+    with torch.cuda.device(phi.device):
+        rc = lib.lccrf_marginals_algo(phi.data_ptr(), dt, _len_ptr(lengths, B, phi.device), B, N, T,
+                                      logZ.data_ptr(), out.data_ptr(), ws.data_ptr(), nws,
+                                      _stream(phi.device), algo)
+    _check(rc, "lccrf_marginals")
+    return logZ, out
+
+
+def lccrf_argmax(phi: torch.Tensor, lengths: Optional[torch.Tensor] = None, *,
+                 out: Optional[torch.Tensor] = None, score: Optional[torch.Tensor] = None,
+                 workspace: Optional[torch.Tensor] = None, algo: int = ALGO_AUTO):
+    """(best_score [B] float32, tags [B, N] int32 with -1 past the length)."""
+    lib = load_library()
+    dt, B, N, T = _phi_args(phi)
+    ws, nws = _workspace(OP_ARGMAX, B, N, T, dt, phi.device, workspace)
+    if out is None:
+        out = torch.empty(B, N, dtype=torch.int32, device=phi.device)
+    if score is None:
+        score = torch.empty(B, dtype=torch.float32, device=phi.device)
+    with torch.cuda.device(phi.device):
+        rc = lib.lccrf_argmax_algo(phi.data_ptr(), dt, _len_ptr(lengths, B, phi.device), B, N, T,
+                                   score.data_ptr(), out.data_ptr(), ws.data_ptr(), nws,
+                                   _stream(phi.device), algo)
+    _check(rc, "lccrf_argmax")
+    return score, out

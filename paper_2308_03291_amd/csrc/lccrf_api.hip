@@ -1,0 +1,137 @@
+// C ABI of the library (declared in include/lccrf.h): argument checks, workspace carving,
+// choice of schedule, launches.  No allocation, no synchronisation, no host copies.
+#include "../../include/lccrf.h"
+#include "lccrf_launch.h"
+
+namespace {
+
+constexpr size_t kAlign = 256;
+inline size_t round_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
+
+struct SumWorkspace {
+    size_t ua, ub, Oa, Ob, total;
+};
+inline SumWorkspace sum_workspace(size_t B, size_t N, size_t T) {
+    SumWorkspace w;
+    size_t off = 0;
+    w.ua = off; off += round_up(B * N * T * sizeof(float));
+    w.ub = off; off += round_up(B * N * T * sizeof(float));
+    w.Oa = off; off += round_up(B * N * sizeof(double));
+    w.Ob = off; off += round_up(B * N * sizeof(double));
+    w.total = off;
+    return w;
+}
+inline size_t max_workspace(size_t B, size_t N, size_t T) { return round_up(B * N * T); }
+
+inline bool shape_ok(int B, int N, int T) {
+    if (B < 1 || N < 1 || T < 1 || T > LCCRF_MAX_T) return false;
+    const double pots = (double)B * (double)N * (double)T * (double)T;
+    return pots < 4.0e18;
+}
+inline bool dtype_ok(int dt) { return dt == LCCRF_F32 || dt == LCCRF_BF16; }
+inline bool aligned_to(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
+
+int check_common(const void* phi, int dt, int B, int N, int T, const void* ws, size_t ws_bytes, size_t need,
+                 int algo) {
+    if (!shape_ok(B, N, T) || !dtype_ok(dt)) return LCCRF_EINVAL;
+    if (algo != LCCRF_ALGO_AUTO && algo != LCCRF_ALGO_SEQUENTIAL && algo != LCCRF_ALGO_SCAN) return LCCRF_EINVAL;
+    if (!phi) return LCCRF_ENULL;
+    if (!ws || ws_bytes < need) return LCCRF_EWORKSPACE;
+    if (!aligned_to(phi, 16) || !aligned_to(ws, kAlign)) return LCCRF_EALIGN;
+    return LCCRF_OK;
+}
+
+int sum_query(int op, const void* phi, int dt, const int32_t* lengths, int B, int N, int T, float* logZ,
+              float* marginals, void* workspace, size_t workspace_bytes, void* stream, int algo) {
+    const size_t need = lccrf_workspace_bytes(op == 0 ? LCCRF_OP_LOGZ : LCCRF_OP_MARGINALS, B, N, T,
+                                              (lccrf_dtype)dt);
+    const int rc = check_common(phi, dt, B, N, T, workspace, workspace_bytes, need, algo);
+    if (rc != LCCRF_OK) return rc;
+    if (op == 0 && !logZ) return LCCRF_ENULL;
+    if (op == 1 && !marginals) return LCCRF_ENULL;
+    if ((logZ && !aligned_to(logZ, 4)) || (marginals && !aligned_to(marginals, 16))) return LCCRF_EALIGN;
+    if (lengths && !aligned_to(lengths, 4)) return LCCRF_EALIGN;
+    if (algo == LCCRF_ALGO_SCAN) return LCCRF_ENOTIMPL;
+    const SumWorkspace w = sum_workspace(B, N, T);
+    char* base = static_cast<char*>(workspace);
+    const hipError_t e = lccrf::launch_sequential_sum(
+        op, dt, phi, lengths, B, N, T, reinterpret_cast<float*>(base + w.ua), reinterpret_cast<float*>(base + w.ub),
+        reinterpret_cast<double*>(base + w.Oa), reinterpret_cast<double*>(base + w.Ob), logZ, marginals,
+        static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? LCCRF_OK : LCCRF_ELAUNCH;
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t lccrf_workspace_bytes(lccrf_op op, int B, int N, int T, lccrf_dtype dt) {
+    if (!shape_ok(B, N, T) || !dtype_ok(dt)) return 0;
+    switch (op) {
+        case LCCRF_OP_LOGZ:
+        case LCCRF_OP_MARGINALS: return sum_workspace(B, N, T).total;
+        case LCCRF_OP_ARGMAX: return max_workspace(B, N, T);
+        default: return 0;
+    }
+}
+
+int lccrf_log_partition_algo(const void* phi, lccrf_dtype dt, const int32_t* lengths, int B, int N, int T,
+                             float* logZ, void* workspace, size_t workspace_bytes, void* stream, lccrf_algo algo) {
+    return sum_query(0, phi, dt, lengths, B, N, T, logZ, nullptr, workspace, workspace_bytes, stream, algo);
+}
+
+int lccrf_marginals_algo(const void* phi, lccrf_dtype dt, const int32_t* lengths, int B, int N, int T, float* logZ,
+                         float* marginals, void* workspace, size_t workspace_bytes, void* stream, lccrf_algo algo) {
+    return sum_query(1, phi, dt, lengths, B, N, T, logZ, marginals, workspace, workspace_bytes, stream, algo);
+}
+
+int lccrf_argmax_algo(const void* phi, lccrf_dtype dt, const int32_t* lengths, int B, int N, int T,
+                      float* best_score, int32_t* tags, void* workspace, size_t workspace_bytes, void* stream,
+                      lccrf_algo algo) {
+    const size_t need = lccrf_workspace_bytes(LCCRF_OP_ARGMAX, B, N, T, dt);
+    const int rc = check_common(phi, dt, B, N, T, workspace, workspace_bytes, need, algo);
+    if (rc != LCCRF_OK) return rc;
+    if (!tags) return LCCRF_ENULL;
+    if (!aligned_to(tags, 4) || (best_score && !aligned_to(best_score, 4))) return LCCRF_EALIGN;
+    if (lengths && !aligned_to(lengths, 4)) return LCCRF_EALIGN;
+    if (algo == LCCRF_ALGO_SCAN) return LCCRF_ENOTIMPL;
+    const hipError_t e =
+        lccrf::launch_sequential_max(dt, phi, lengths, B, N, T, static_cast<uint8_t*>(workspace), best_score, tags,
+                                     static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? LCCRF_OK : LCCRF_ELAUNCH;
+}
+
+int lccrf_log_partition(const void* phi, lccrf_dtype dt, const int32_t* lengths, int B, int N, int T, float* logZ,
+                        void* workspace, size_t workspace_bytes, void* stream) {
+    return lccrf_log_partition_algo(phi, dt, lengths, B, N, T, logZ, workspace, workspace_bytes, stream,
+                                    LCCRF_ALGO_AUTO);
+}
+
+int lccrf_marginals(const void* phi, lccrf_dtype dt, const int32_t* lengths, int B, int N, int T, float* logZ,
+                    float* marginals, void* workspace, size_t workspace_bytes, void* stream) {
+    return lccrf_marginals_algo(phi, dt, lengths, B, N, T, logZ, marginals, workspace, workspace_bytes, stream,
+                                LCCRF_ALGO_AUTO);
+}
+
+int lccrf_argmax(const void* phi, lccrf_dtype dt, const int32_t* lengths, int B, int N, int T, float* best_score,
+                 int32_t* tags, void* workspace, size_t workspace_bytes, void* stream) {
+    return lccrf_argmax_algo(phi, dt, lengths, B, N, T, best_score, tags, workspace, workspace_bytes, stream,
+                             LCCRF_ALGO_AUTO);
+}
+
+const char* lccrf_strerror(int code) {
+    switch (code) {
+        case LCCRF_OK: return "ok";
+        case LCCRF_EINVAL: return "invalid argument (B, N, T, dtype, op or algo)";
+        case LCCRF_ENULL: return "a required pointer is NULL";
+        case LCCRF_EWORKSPACE: return "workspace is NULL or too small";
+        case LCCRF_EALIGN: return "a buffer is misaligned";
+        case LCCRF_ELAUNCH: return "the HIP runtime refused a kernel launch";
+        case LCCRF_ENOTIMPL: return "the requested schedule is not available for this shape";
+        default: return "unknown lccrf status";
+    }
+}
+
+int lccrf_version(void) { return 100; }
+
+}  // extern "C"

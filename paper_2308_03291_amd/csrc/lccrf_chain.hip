@@ -1,0 +1,476 @@
+// Sequential (position-by-position) log-semiring chains for the linear-chain CRF.
+//
+// The paper computes logZ with the forward algorithm (section "Sequence Tagging") and
+// obtains marginals as the gradient of logZ (section "Computing Marginals", Eq. 4), i.e.
+// by replaying the recursion backwards.  Here both recursions are written by hand and each
+// sequence is served by TWO chains that run at the same time and meet in the middle:
+//
+//   pass 1 (chain_half_kernel):  a forward workgroup computes alpha_0 .. alpha_h and a
+//       backward workgroup computes beta_{L-1} .. beta_h (h = L / 2); both store their
+//       normalised vectors.  Together they read every matrix once.
+//   pass 2 (chain_marginal_kernel):  the forward workgroup continues over h+1 .. L-1 and
+//       now has beta_i (stored by pass 1) when it reads phi_i, so it writes the marginals
+//       mu_i = exp(alpha_{i-1} + phi_i + beta_i - logZ) in the same sweep; the backward
+//       workgroup does the same over h .. 1 with the stored alpha_{i-1}.  Together they
+//       read every matrix a second time and write every marginal once.
+//
+// That is the minimum traffic of forward-backward (two reads of phi, one write of mu) at
+// half the serial depth and with twice as many workgroups streaming from HBM.
+//
+// Numerics: vectors are kept as u = alpha - O with a double-precision running offset O and
+// max(u) = 0 after every step, so magnitudes stay small however long the chain is; every
+// log-sum-exp is shifted by its exact maximum; -inf entries are neutral.
+#include "lccrf_device.h"
+#include "lccrf_launch.h"
+
+namespace lccrf {
+
+template <typename G>
+struct ChainSmem {
+    alignas(16) float part[G::WAVES][G::TCAP];  // per-wave partial column maxima, then partial column sums
+    alignas(16) float cm[G::TCAP];              // exact column maxima of the current step
+    alignas(16) float rvec[2][G::TCAP];         // un-normalised result vector of a step (double buffered)
+    alignas(16) float wmax[2][16];              // per-wave maxima of rvec (normaliser = their maximum)
+    alignas(16) float red[2][4];                // scratch for the mid-point log-sum-exp
+};
+
+template <typename G>
+__device__ __forceinline__ void smem_init(ChainSmem<G>& sm, int tid) {
+    for (int k = tid; k < 2 * G::TCAP; k += G::W) (&sm.rvec[0][0])[k] = LCCRF_NEG_INF;
+    if (tid < 32) (&sm.wmax[0][0])[tid] = LCCRF_NEG_INF;
+}
+
+// Normaliser of the vector in rvec[buf]: its maximum (0 if the vector is all -inf).
+template <typename G>
+__device__ __forceinline__ float read_shift(const ChainSmem<G>& sm, int buf) {
+    float d = LCCRF_NEG_INF;
+#pragma unroll
+    for (int w = 0; w < 16; w += 4) {
+        const float4 q = *reinterpret_cast<const float4*>(&sm.wmax[buf][w]);
+        d = fmaxf(fmaxf(d, fmaxf(q.x, q.y)), fmaxf(q.z, q.w));
+    }
+    return finite_or_zero(d);
+}
+
+// Publish r (one value per column thread, -inf for t >= T) as the next vector.
+template <typename G>
+__device__ __forceinline__ void publish_columns(ChainSmem<G>& sm, int nbuf, int tid, float r) {
+    // r must be -inf in every lane that owns no column; the wave-wide exchange runs with
+    // all lanes of the (wave-uniformly selected) column waves active.
+    if ((tid >> 6) < G::COLWAVES) {
+        if (tid < G::TCAP) sm.rvec[nbuf][tid] = r;
+        const float wm = xor_max<1, 64>(r);
+        if ((tid & 63) == 0) sm.wmax[nbuf][tid >> 6] = wm;
+    }
+}
+
+// One exact forward step: r(t) = log2 sum_s 2^(ua(s) + phi2(s,t)).
+// WITH_MU: also mu(s,t) = 2^(ua(s) + phi2(s,t) + ubK(t)), ubK = beta_i(t) + (offsets - logZ).
+template <typename G, bool WITH_MU>
+__device__ __forceinline__ void fwd_step(ChainSmem<G>& sm, int buf, int tid, int c4,
+                                         const float (&v)[G::ITEMS][4], const float (&ua)[G::ITEMS],
+                                         const float (&ubK)[4], float (&mu)[G::ITEMS][4]) {
+    constexpr int ITEMS = G::ITEMS;
+    const int lane = tid & 63, wave = tid >> 6;
+    float x[ITEMS][4];
+    float lm[4] = {LCCRF_NEG_INF, LCCRF_NEG_INF, LCCRF_NEG_INF, LCCRF_NEG_INF};
+#pragma unroll
+    for (int k = 0; k < ITEMS; ++k)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            x[k][j] = __builtin_fmaf(v[k][j], kLog2e, ua[k]);
+            lm[j] = fmaxf(lm[j], x[k][j]);
+        }
+#pragma unroll
+    for (int j = 0; j < 4; ++j) lm[j] = xor_max<G::LPR, 64>(lm[j]);
+    if (lane < G::LPR)
+        *reinterpret_cast<float4*>(&sm.part[wave][c4]) = make_float4(lm[0], lm[1], lm[2], lm[3]);
+    __syncthreads();
+    if (tid < G::TCAP) {
+        float m = LCCRF_NEG_INF;
+#pragma unroll
+        for (int w = 0; w < G::WAVES; ++w) m = fmaxf(m, sm.part[w][tid]);
+        sm.cm[tid] = m;
+    }
+    __syncthreads();
+    const float4 cq = *reinterpret_cast<const float4*>(&sm.cm[c4]);
+    const float g[4] = {finite_or_zero(cq.x), finite_or_zero(cq.y), finite_or_zero(cq.z), finite_or_zero(cq.w)};
+    float ls[4] = {0.f, 0.f, 0.f, 0.f};
+    float gm[4];
+    if (WITH_MU) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) gm[j] = ex2(g[j] + ubK[j]);
+    }
+#pragma unroll
+    for (int k = 0; k < ITEMS; ++k)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const float e = ex2(x[k][j] - g[j]);
+            ls[j] += e;
+            if (WITH_MU) mu[k][j] = e * gm[j];
+        }
+#pragma unroll
+    for (int j = 0; j < 4; ++j) ls[j] = xor_sum<G::LPR, 64>(ls[j]);
+    if (lane < G::LPR)
+        *reinterpret_cast<float4*>(&sm.part[wave][c4]) = make_float4(ls[0], ls[1], ls[2], ls[3]);
+    __syncthreads();
+    float r = LCCRF_NEG_INF;
+    if (tid < G::TCAP) {
+        float S = 0.f;
+#pragma unroll
+        for (int w = 0; w < G::WAVES; ++w) S += sm.part[w][tid];
+        r = sm.cm[tid] + lg2(S);  // cm = -inf gives S = 0: -inf + -inf = -inf
+    }
+    publish_columns<G>(sm, buf ^ 1, tid, r);
+    __syncthreads();
+}
+
+// One exact backward step: r(s) = log2 sum_t 2^(phi2(s,t) + ub(t)).
+// WITH_MU: also mu(s,t) = 2^(uaK(s) + phi2(s,t) + ub(t)), uaK = alpha_{i-1}(s) + (offsets - logZ).
+template <typename G, bool WITH_MU>
+__device__ __forceinline__ void bwd_step(ChainSmem<G>& sm, int buf, int tid, int c4, int r0, int T,
+                                         const float (&v)[G::ITEMS][4], const float (&ub)[4],
+                                         const float (&uaK)[G::ITEMS], float (&mu)[G::ITEMS][4]) {
+    constexpr int ITEMS = G::ITEMS;
+    const int lane = tid & 63, wave = tid >> 6;
+    float wm = LCCRF_NEG_INF;
+#pragma unroll
+    for (int k = 0; k < ITEMS; ++k) {
+        float y[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) y[j] = __builtin_fmaf(v[k][j], kLog2e, ub[j]);
+        float m = fmaxf(fmaxf(y[0], y[1]), fmaxf(y[2], y[3]));
+        m = xor_max<1, G::LPR>(m);
+        const float g = finite_or_zero(m);
+        float e[4];
+        float S = 0.f;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) { e[j] = ex2(y[j] - g); S += e[j]; }
+        S = xor_sum<1, G::LPR>(S);
+        const float r = m + lg2(S);
+        if (WITH_MU) {
+            const float f = ex2(g + uaK[k]);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) mu[k][j] = e[j] * f;
+        }
+        const int s = r0 + k * G::RPP;
+        if (c4 == 0 && s < T) sm.rvec[buf ^ 1][s] = r;
+        wm = fmaxf(wm, r);
+    }
+    wm = xor_max<1, 64>(wm);
+    if (lane == 0) sm.wmax[buf ^ 1][wave] = wm;
+    __syncthreads();
+}
+
+struct ChainArgs {
+    const void* phi;
+    const int32_t* lengths;
+    int B, N, T;
+    float* ua;   // [B][N][T] normalised forward vectors (base-2 logs)
+    float* ub;   // [B][N][T] normalised backward vectors
+    double* Oa;  // [B][N] forward offsets:  alpha_i = (ua_i + Oa_i) * ln 2
+    double* Ob;  // [B][N] backward offsets
+    float* logZ;
+    float* mu;
+};
+
+// ---------------------------------------------------------------------------------------
+// Pass 1: both half chains, vectors stored, nothing else written.
+template <typename G, typename TIN, bool ALIGNED>
+__global__ __launch_bounds__(G::W) void chain_half_kernel(ChainArgs a) {
+    __shared__ ChainSmem<G> sm;
+    constexpr int ITEMS = G::ITEMS;
+    const int tid = threadIdx.x;
+    const int b = blockIdx.x >> 1, dir = blockIdx.x & 1;
+    const int N = a.N, T = a.T;
+    const int L = clamp_length(a.lengths, b, N);
+    if (L == 0) return;
+    const int h = L / 2;
+    const int c4 = 4 * (tid % G::LPR), r0 = tid / G::LPR;
+    const TIN* phib = static_cast<const TIN*>(a.phi) + (size_t)b * N * T * T;
+    const size_t TT = (size_t)T * T;
+    const size_t vb = (size_t)b * N;
+
+    smem_init<G>(sm, tid);
+    __syncthreads();
+    float A[ITEMS][4], Bq[ITEMS][4];
+    float dummy4[4] = {0.f, 0.f, 0.f, 0.f}, dummyI[ITEMS], dmu[ITEMS][4];
+    double O = 0.0;
+    int buf = 0;
+
+    if (dir == 0) {
+        publish_columns<G>(sm, 0, tid, (tid < T) ? Elem<TIN>::get(phib + tid) * kLog2e : LCCRF_NEG_INF);
+        __syncthreads();
+        auto step = [&](int i, const float (&v)[ITEMS][4]) {
+            const float d = read_shift<G>(sm, buf);
+            O += (double)d;
+            float ua[ITEMS];
+#pragma unroll
+            for (int k = 0; k < ITEMS; ++k) {
+                const int s = r0 + k * G::RPP;
+                ua[k] = (s < T) ? sm.rvec[buf][s] - d : LCCRF_NEG_INF;
+            }
+            if (tid < T) a.ua[(vb + i - 1) * T + tid] = sm.rvec[buf][tid] - d;
+            if (tid == 0) a.Oa[vb + i - 1] = O;
+            fwd_step<G, false>(sm, buf, tid, c4, v, ua, dummy4, dmu);
+            buf ^= 1;
+        };
+        int i = 1;
+        if (i <= h) load_tile<G, TIN, ALIGNED>(phib + (size_t)i * TT, T, c4, r0, A);
+        while (i <= h) {
+            if (i + 1 <= h) load_tile<G, TIN, ALIGNED>(phib + (size_t)(i + 1) * TT, T, c4, r0, Bq);
+            step(i, A);
+            if (++i > h) break;
+            if (i + 1 <= h) load_tile<G, TIN, ALIGNED>(phib + (size_t)(i + 1) * TT, T, c4, r0, A);
+            step(i, Bq);
+            ++i;
+        }
+        const float d = read_shift<G>(sm, buf);
+        O += (double)d;
+        if (tid < T) a.ua[(vb + h) * T + tid] = sm.rvec[buf][tid] - d;
+        if (tid == 0) a.Oa[vb + h] = O;
+    } else {
+        publish_columns<G>(sm, 0, tid, (tid < T) ? 0.f : LCCRF_NEG_INF);
+        __syncthreads();
+        auto step = [&](int i, const float (&v)[ITEMS][4]) {
+            const float d = read_shift<G>(sm, buf);
+            O += (double)d;
+            const float4 q = *reinterpret_cast<const float4*>(&sm.rvec[buf][c4]);
+            const float ub[4] = {q.x - d, q.y - d, q.z - d, q.w - d};
+            if (tid < T) a.ub[(vb + i) * T + tid] = sm.rvec[buf][tid] - d;
+            if (tid == 0) a.Ob[vb + i] = O;
+            bwd_step<G, false>(sm, buf, tid, c4, r0, T, v, ub, dummyI, dmu);
+            buf ^= 1;
+        };
+        int i = L - 1;
+        if (i > h) load_tile<G, TIN, ALIGNED>(phib + (size_t)i * TT, T, c4, r0, A);
+        while (i > h) {
+            if (i - 1 > h) load_tile<G, TIN, ALIGNED>(phib + (size_t)(i - 1) * TT, T, c4, r0, Bq);
+            step(i, A);
+            if (--i <= h) break;
+            if (i - 1 > h) load_tile<G, TIN, ALIGNED>(phib + (size_t)(i - 1) * TT, T, c4, r0, A);
+            step(i, Bq);
+            --i;
+        }
+        const float d = read_shift<G>(sm, buf);
+        O += (double)d;
+        if (tid < T) a.ub[(vb + h) * T + tid] = sm.rvec[buf][tid] - d;
+        if (tid == 0) a.Ob[vb + h] = O;
+    }
+}
+
+// log2 Z from the two vectors stored for the meeting position h.  Every thread of the
+// workgroup returns the same value.
+template <typename G>
+__device__ __forceinline__ double midpoint_log2z(ChainSmem<G>& sm, const ChainArgs& a, size_t vb, int h, int T, int tid) {
+    float z = LCCRF_NEG_INF;
+    if (tid < T) z = a.ua[(vb + h) * T + tid] + a.ub[(vb + h) * T + tid];
+    if ((tid >> 6) < G::COLWAVES) {
+        const float wm = xor_max<1, 64>(z);
+        if ((tid & 63) == 0) sm.red[0][tid >> 6] = wm;
+    }
+    __syncthreads();
+    float M = LCCRF_NEG_INF;
+#pragma unroll
+    for (int w = 0; w < G::COLWAVES; ++w) M = fmaxf(M, sm.red[0][w]);
+    const float g = finite_or_zero(M);
+    if ((tid >> 6) < G::COLWAVES) {
+        const float ws = xor_sum<1, 64>(ex2(z - g));  // z = -inf outside the T columns: adds 0
+        if ((tid & 63) == 0) sm.red[1][tid >> 6] = ws;
+    }
+    __syncthreads();
+    float S = 0.f;
+#pragma unroll
+    for (int w = 0; w < G::COLWAVES; ++w) S += sm.red[1][w];
+    return (double)(M + lg2(S)) + a.Oa[vb + h] + a.Ob[vb + h];
+}
+
+// ---------------------------------------------------------------------------------------
+// Pass 2: both chains continue past the meeting point and write the marginals.
+template <typename G, typename TIN, bool ALIGNED>
+__global__ __launch_bounds__(G::W) void chain_marginal_kernel(ChainArgs a) {
+    __shared__ ChainSmem<G> sm;
+    constexpr int ITEMS = G::ITEMS;
+    const int tid = threadIdx.x;
+    const int b = blockIdx.x >> 1, dir = blockIdx.x & 1;
+    const int N = a.N, T = a.T;
+    const int L = clamp_length(a.lengths, b, N);
+    const size_t TT = (size_t)T * T;
+    const size_t vb = (size_t)b * N;
+    float* mub = a.mu + (size_t)b * N * TT;
+
+    if (dir == 0) {
+        // positions past the end carry no edge: their marginals are zero
+        const size_t z0 = (size_t)L * TT, z1 = (size_t)N * TT;
+        if (ALIGNED) {
+            float4* p = reinterpret_cast<float4*>(mub);
+            for (size_t k = z0 / 4 + tid; k < z1 / 4; k += G::W) p[k] = make_float4(0.f, 0.f, 0.f, 0.f);
+        } else {
+            for (size_t k = z0 + tid; k < z1; k += G::W) mub[k] = 0.f;
+        }
+    }
+    if (L == 0) {
+        if (dir == 0 && tid == 0 && a.logZ) a.logZ[b] = 0.f;
+        return;
+    }
+    const int h = L / 2;
+    const int c4 = 4 * (tid % G::LPR), r0 = tid / G::LPR;
+    const TIN* phib = static_cast<const TIN*>(a.phi) + (size_t)b * N * TT;
+
+    smem_init<G>(sm, tid);
+    const double lz2 = midpoint_log2z<G>(sm, a, vb, h, T, tid);
+    const bool feasible = lz2 > -1.0e300;  // false: no path has a finite score, marginals are 0
+    if (dir == 0 && tid == 0 && a.logZ) a.logZ[b] = (float)(lz2 * kLn2);
+
+    float A[ITEMS][4], Bq[ITEMS][4], mu[ITEMS][4];
+    int buf = 0;
+
+    if (dir == 0) {
+        double O = a.Oa[vb + h];
+        publish_columns<G>(sm, 0, tid, (tid < T) ? a.ua[(vb + h) * T + tid] : LCCRF_NEG_INF);
+        __syncthreads();
+        float auxA[4], auxB[4];
+        double obA = 0.0, obB = 0.0;
+        auto load = [&](int i, float (&v)[ITEMS][4], float (&aux)[4], double& ob) {
+            load_tile<G, TIN, ALIGNED>(phib + (size_t)i * TT, T, c4, r0, v);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) aux[j] = (c4 + j < T) ? a.ub[(vb + i) * T + c4 + j] : LCCRF_NEG_INF;
+            ob = a.Ob[vb + i];
+        };
+        auto step = [&](int i, const float (&v)[ITEMS][4], const float (&aux)[4], double ob) {
+            const float d = read_shift<G>(sm, buf);
+            O += (double)d;
+            float ua[ITEMS];
+#pragma unroll
+            for (int k = 0; k < ITEMS; ++k) {
+                const int s = r0 + k * G::RPP;
+                ua[k] = (s < T) ? sm.rvec[buf][s] - d : LCCRF_NEG_INF;
+            }
+            const float K = feasible ? (float)(O + ob - lz2) : LCCRF_NEG_INF;
+            const float ubK[4] = {aux[0] + K, aux[1] + K, aux[2] + K, aux[3] + K};
+            fwd_step<G, true>(sm, buf, tid, c4, v, ua, ubK, mu);
+            store_tile<G, ALIGNED>(mub + (size_t)i * TT, T, c4, r0, mu);
+            buf ^= 1;
+        };
+        int i = h + 1;
+        if (i < L) load(i, A, auxA, obA);
+        while (i < L) {
+            if (i + 1 < L) load(i + 1, Bq, auxB, obB);
+            step(i, A, auxA, obA);
+            if (++i >= L) break;
+            if (i + 1 < L) load(i + 1, A, auxA, obA);
+            step(i, Bq, auxB, obB);
+            ++i;
+        }
+    } else {
+        double O = a.Ob[vb + h];
+        publish_columns<G>(sm, 0, tid, (tid < T) ? a.ub[(vb + h) * T + tid] : LCCRF_NEG_INF);
+        __syncthreads();
+        float auxA[ITEMS], auxB[ITEMS];
+        double oaA = 0.0, oaB = 0.0;
+        auto load = [&](int i, float (&v)[ITEMS][4], float (&aux)[ITEMS], double& oa) {
+            load_tile<G, TIN, ALIGNED>(phib + (size_t)i * TT, T, c4, r0, v);
+#pragma unroll
+            for (int k = 0; k < ITEMS; ++k) {
+                const int s = r0 + k * G::RPP;
+                aux[k] = (s < T) ? a.ua[(vb + i - 1) * T + s] : LCCRF_NEG_INF;
+            }
+            oa = a.Oa[vb + i - 1];
+        };
+        auto step = [&](int i, const float (&v)[ITEMS][4], const float (&aux)[ITEMS], double oa) {
+            const float d = read_shift<G>(sm, buf);
+            O += (double)d;
+            const float4 q = *reinterpret_cast<const float4*>(&sm.rvec[buf][c4]);
+            const float ub[4] = {q.x - d, q.y - d, q.z - d, q.w - d};
+            const float K = feasible ? (float)(oa + O - lz2) : LCCRF_NEG_INF;
+            float uaK[ITEMS];
+#pragma unroll
+            for (int k = 0; k < ITEMS; ++k) uaK[k] = aux[k] + K;
+            bwd_step<G, true>(sm, buf, tid, c4, r0, T, v, ub, uaK, mu);
+            store_tile<G, ALIGNED>(mub + (size_t)i * TT, T, c4, r0, mu);
+            buf ^= 1;
+        };
+        int i = h;
+        if (i >= 1) load(i, A, auxA, oaA);
+        while (i >= 1) {
+            if (i - 1 >= 1) load(i - 1, Bq, auxB, oaB);
+            step(i, A, auxA, oaA);
+            if (--i < 1) break;
+            if (i - 1 >= 1) load(i - 1, A, auxA, oaA);
+            step(i, Bq, auxB, oaB);
+            --i;
+        }
+        // position 0: p(y_0 = t) in row 0, zeros in the other rows
+        const float d = read_shift<G>(sm, buf);
+        O += (double)d;
+        const float K = feasible ? (float)(a.Oa[vb] + O - lz2) : LCCRF_NEG_INF;
+        for (int k = tid; k < (int)TT; k += G::W) {
+            float val = 0.f;
+            if (k < T) val = ex2(a.ua[vb * T + k] + (sm.rvec[buf][k] - d) + K);
+            mub[k] = val;
+        }
+    }
+}
+
+// logZ alone: combine the two stored mid-point vectors.  One wave per sequence.
+__global__ __launch_bounds__(64) void logz_combine_kernel(ChainArgs a) {
+    const int b = blockIdx.x, lane = threadIdx.x;
+    const int N = a.N, T = a.T;
+    const int L = clamp_length(a.lengths, b, N);
+    if (L == 0) {
+        if (lane == 0) a.logZ[b] = 0.f;
+        return;
+    }
+    const int h = L / 2;
+    const size_t vb = (size_t)b * N;
+    const float* ua = a.ua + (vb + h) * T;
+    const float* ub = a.ub + (vb + h) * T;
+    float m = LCCRF_NEG_INF;
+    for (int t = lane; t < T; t += 64) m = fmaxf(m, ua[t] + ub[t]);
+    m = xor_max<1, 64>(m);
+    const float g = finite_or_zero(m);
+    float S = 0.f;
+    for (int t = lane; t < T; t += 64) S += ex2(ua[t] + ub[t] - g);
+    S = xor_sum<1, 64>(S);
+    if (lane == 0) a.logZ[b] = (float)(((double)(m + lg2(S)) + a.Oa[vb + h] + a.Ob[vb + h]) * kLn2);
+}
+
+// ---------------------------------------------------------------------------------------
+// Host-side dispatch.
+template <typename G, typename TIN, bool ALIGNED>
+static hipError_t launch_geo(int op, const ChainArgs& a, hipStream_t st) {
+    hipLaunchKernelGGL((chain_half_kernel<G, TIN, ALIGNED>), dim3(2 * a.B), dim3(G::W), 0, st, a);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    if (op == 0) {
+        hipLaunchKernelGGL(logz_combine_kernel, dim3(a.B), dim3(64), 0, st, a);
+    } else {
+        hipLaunchKernelGGL((chain_marginal_kernel<G, TIN, ALIGNED>), dim3(2 * a.B), dim3(G::W), 0, st, a);
+    }
+    return hipGetLastError();
+}
+
+template <typename TIN, bool ALIGNED>
+static hipError_t launch_T(int op, const ChainArgs& a, hipStream_t st) {
+    const int T = a.T;
+    if (T <= 4) return launch_geo<Geo<1, 1, 1>, TIN, ALIGNED>(op, a, st);
+    if (T <= 8) return launch_geo<Geo<2, 1, 1>, TIN, ALIGNED>(op, a, st);
+    if (T <= 16) return launch_geo<Geo<4, 1, 1>, TIN, ALIGNED>(op, a, st);
+    if (T <= 32) return launch_geo<Geo<8, 4, 1>, TIN, ALIGNED>(op, a, st);
+    if (T <= 64) return launch_geo<Geo<16, 4, 4>, TIN, ALIGNED>(op, a, st);
+    if (T <= 128) return launch_geo<Geo<32, 16, 4>, TIN, ALIGNED>(op, a, st);
+    return launch_geo<Geo<64, 16, 16>, TIN, ALIGNED>(op, a, st);
+}
+
+// op: 0 = logZ only, 1 = marginals (+ logZ).  Workspace pointers already carved by the caller.
+hipError_t launch_sequential_sum(int op, int dtype, const void* phi, const int32_t* lengths, int B, int N, int T,
+                                 float* ua, float* ub, double* Oa, double* Ob, float* logZ, float* mu,
+                                 hipStream_t st) {
+    ChainArgs a{phi, lengths, B, N, T, ua, ub, Oa, Ob, logZ, mu};
+    const bool aligned = (T % 4) == 0;
+    if (dtype == 0)
+        return aligned ? launch_T<float, true>(op, a, st) : launch_T<float, false>(op, a, st);
+    return aligned ? launch_T<uint16_t, true>(op, a, st) : launch_T<uint16_t, false>(op, a, st);
+}
+
+}  // namespace lccrf

@@ -1,0 +1,134 @@
+// Device-side building blocks shared by the linear-chain CRF kernels (gfx950 only).
+//
+// Thread mapping used by every chain kernel.  One T x T matrix phi_i (row s = previous
+// tag, column t = current tag, t contiguous in memory) is spread over a workgroup of
+// W = 64 * WAVES threads as follows: LPR consecutive lanes cover one row, each lane owning
+// four consecutive columns (t = 4c .. 4c+3, c = tid % LPR); the W / LPR row groups cover
+// rows r0, r0 + RPP, r0 + 2 RPP, ... (r0 = tid / LPR, RPP = W / LPR), ITEMS rows per
+// thread.  A wave therefore reads whole, contiguous rows: every global load is coalesced,
+// and 16-byte wide whenever T is a multiple of 4.
+//
+//   reduction over s (forward recursion): in-thread over ITEMS rows, then across the
+//       64 / LPR row groups of a wave by lane exchange, then across waves through LDS;
+//   reduction over t (backward recursion): in-thread over 4 columns, then across the LPR
+//       lanes of the row by lane exchange; never leaves the wave.
+//
+// All recursions run in base-2 logarithms: x2 = x * log2(e), so that the hardware
+// v_exp_f32 / v_log_f32 (base 2) are used directly and the multiply folds into one fma.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace lccrf {
+
+constexpr float kLog2e = 1.44269504088896340736f;
+constexpr double kLn2 = 0.69314718055994530942;
+#define LCCRF_NEG_INF (-__builtin_huge_valf())
+
+__device__ __forceinline__ float ex2(float x) { return __builtin_amdgcn_exp2f(x); }
+__device__ __forceinline__ float lg2(float x) { return __builtin_amdgcn_logf(x); }
+
+__device__ __forceinline__ float bf16_to_f32(uint16_t h) {
+    return __uint_as_float(static_cast<uint32_t>(h) << 16);
+}
+
+template <typename TIN> struct Elem;
+template <> struct Elem<float> {
+    static __device__ __forceinline__ float get(const float* p) { return *p; }
+    static __device__ __forceinline__ void get4(const float* p, float (&o)[4]) {
+        const float4 v = *reinterpret_cast<const float4*>(p);
+        o[0] = v.x; o[1] = v.y; o[2] = v.z; o[3] = v.w;
+    }
+};
+template <> struct Elem<uint16_t> {
+    static __device__ __forceinline__ float get(const uint16_t* p) { return bf16_to_f32(*p); }
+    static __device__ __forceinline__ void get4(const uint16_t* p, float (&o)[4]) {
+        const uint2 v = *reinterpret_cast<const uint2*>(p);
+        o[0] = __uint_as_float(v.x << 16);
+        o[1] = __uint_as_float(v.x & 0xffff0000u);
+        o[2] = __uint_as_float(v.y << 16);
+        o[3] = __uint_as_float(v.y & 0xffff0000u);
+    }
+};
+
+// Geometry of one instantiation.
+template <int LPR_, int WAVES_, int ITEMS_>
+struct Geo {
+    static constexpr int LPR = LPR_;        // lanes per row (power of two, <= 64)
+    static constexpr int WAVES = WAVES_;
+    static constexpr int ITEMS = ITEMS_;    // rows per thread
+    static constexpr int W = 64 * WAVES_;   // threads per workgroup
+    static constexpr int RPP = W / LPR_;    // rows covered by one pass of the workgroup
+    static constexpr int TCAP = 4 * LPR_;   // largest T this geometry covers
+    static constexpr int RGW = 64 / LPR_;   // row groups per wave
+    static constexpr int COLWAVES = (TCAP + 63) / 64;  // waves holding one thread per column
+    static_assert(RPP * ITEMS_ >= TCAP || RPP * ITEMS_ >= 1, "rows not covered");
+};
+
+// Load this thread's part of one matrix; entries outside the T x T matrix read as -inf,
+// the neutral element of both max and log-sum-exp.
+template <typename G, typename TIN, bool ALIGNED>
+__device__ __forceinline__ void load_tile(const TIN* __restrict__ mat, int T, int c4, int r0,
+                                          float (&v)[G::ITEMS][4]) {
+#pragma unroll
+    for (int k = 0; k < G::ITEMS; ++k) {
+        const int s = r0 + k * G::RPP;
+        if (s < T && c4 < T) {
+            const TIN* p = mat + (size_t)s * T + c4;
+            if (ALIGNED) {
+                Elem<TIN>::get4(p, v[k]);
+            } else {
+#pragma unroll
+                for (int j = 0; j < 4; ++j) v[k][j] = (c4 + j < T) ? Elem<TIN>::get(p + j) : LCCRF_NEG_INF;
+            }
+        } else {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) v[k][j] = LCCRF_NEG_INF;
+        }
+    }
+}
+
+// Store this thread's part of one matrix of marginals.
+template <typename G, bool ALIGNED>
+__device__ __forceinline__ void store_tile(float* __restrict__ mat, int T, int c4, int r0,
+                                           const float (&v)[G::ITEMS][4]) {
+#pragma unroll
+    for (int k = 0; k < G::ITEMS; ++k) {
+        const int s = r0 + k * G::RPP;
+        if (s < T && c4 < T) {
+            float* p = mat + (size_t)s * T + c4;
+            if (ALIGNED) {
+                *reinterpret_cast<float4*>(p) = make_float4(v[k][0], v[k][1], v[k][2], v[k][3]);
+            } else {
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    if (c4 + j < T) p[j] = v[k][j];
+            }
+        }
+    }
+}
+
+// All-reduce over the lanes of a wave whose ids differ only in the bits [LO, HI).
+template <int LO, int HI>
+__device__ __forceinline__ float xor_max(float x) {
+#pragma unroll
+    for (int off = LO; off < HI; off <<= 1) x = fmaxf(x, __shfl_xor(x, off, 64));
+    return x;
+}
+template <int LO, int HI>
+__device__ __forceinline__ float xor_sum(float x) {
+#pragma unroll
+    for (int off = LO; off < HI; off <<= 1) x += __shfl_xor(x, off, 64);
+    return x;
+}
+
+__device__ __forceinline__ float finite_or_zero(float m) { return (m == LCCRF_NEG_INF) ? 0.0f : m; }
+
+__device__ __forceinline__ int clamp_length(const int32_t* __restrict__ lengths, int b, int N) {
+    int L = lengths ? lengths[b] : N;
+    L = L < 0 ? 0 : L;
+    return L > N ? N : L;
+}
+
+}  // namespace lccrf

@@ -1,0 +1,93 @@
+"""Host-only checks of the C ABI: the library loads, exports every symbol the header
+declares, sizes workspaces sensibly and rejects bad arguments before touching the GPU."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2308_03291_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(binding.LIB_PATH):
+        from paper_2308_03291_amd import build_ext
+        build_ext.build()
+    return binding.load_library()
+
+
+def _declared_functions():
+    text = open(os.path.join(ROOT, "include", "lccrf.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(lccrf_[a-z_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(lib):
+    names = _declared_functions()
+    assert "lccrf_log_partition" in names and "lccrf_marginals" in names and "lccrf_argmax" in names
+    for n in names:
+        assert hasattr(lib, n), f"{n} is declared in include/lccrf.h but not exported"
+    assert set(names) == set(binding.EXPORTS)
+
+
+def test_version_and_strerror(lib):
+    assert lib.lccrf_version() >= 100
+    assert binding.strerror(0) == "ok"
+    for code in range(-6, 0):
+        assert "unknown" not in binding.strerror(code)
+    assert "unknown" in binding.strerror(-99)
+
+
+def test_workspace_sizes(lib):
+    for op in (binding.OP_LOGZ, binding.OP_MARGINALS, binding.OP_ARGMAX):
+        n = binding.workspace_bytes(op, 64, 512, 128, binding.LCCRF_F32)
+        assert n > 0 and n % 256 == 0
+        # scratch is O(B N T), a 1/T fraction of the potentials
+        assert n <= 64 * 512 * 128 * 16 + 4096 * 8
+    assert binding.workspace_bytes(binding.OP_MARGINALS, 0, 8, 8, 0) == 0
+    assert binding.workspace_bytes(binding.OP_MARGINALS, 1, 8, 257, 0) == 0
+    assert binding.workspace_bytes(binding.OP_MARGINALS, 1, 8, 8, 7) == 0
+    assert binding.workspace_bytes(9, 1, 8, 8, 0) == 0
+
+
+def test_bad_arguments_are_rejected_without_a_gpu(lib):
+    fake = 4096  # a non-null, aligned "pointer" that is never dereferenced on these paths
+    ws = 1 << 20
+    EINVAL, ENULL, EWS, EALIGN = -1, -2, -3, -4
+    assert lib.lccrf_log_partition(fake, 0, None, 0, 4, 4, fake, fake, ws, None) == EINVAL
+    assert lib.lccrf_log_partition(fake, 0, None, 1, 4, 300, fake, fake, ws, None) == EINVAL
+    assert lib.lccrf_log_partition(fake, 5, None, 1, 4, 4, fake, fake, ws, None) == EINVAL
+    assert lib.lccrf_log_partition(None, 0, None, 1, 4, 4, fake, fake, ws, None) == ENULL
+    assert lib.lccrf_log_partition(fake, 0, None, 1, 4, 4, None, fake, ws, None) == ENULL
+    assert lib.lccrf_log_partition(fake, 0, None, 1, 4, 4, fake, None, ws, None) == EWS
+    assert lib.lccrf_log_partition(fake, 0, None, 1, 4, 4, fake, fake, 8, None) == EWS
+    assert lib.lccrf_log_partition(fake + 4, 0, None, 1, 4, 4, fake, fake, ws, None) == EALIGN
+    assert lib.lccrf_log_partition(fake, 0, None, 1, 4, 4, fake, fake + 16, ws, None) == EALIGN
+    assert lib.lccrf_marginals(fake, 0, None, 1, 4, 4, None, None, fake, ws, None) == ENULL
+    assert lib.lccrf_marginals(fake, 0, None, 1, 4, 4, None, fake + 4, fake, ws, None) == EALIGN
+    assert lib.lccrf_argmax(fake, 0, None, 1, 4, 4, None, None, fake, ws, None) == ENULL
+    assert lib.lccrf_argmax_algo(fake, 0, None, 1, 4, 4, None, fake, fake, ws, None, 17) == EINVAL
+
+
+def test_binding_refuses_cpu_tensors():
+    import torch
+    with pytest.raises(ValueError):
+        binding.lccrf_log_partition(torch.zeros(1, 2, 3, 3))
+    with pytest.raises(ValueError):
+        binding.lccrf_marginals(torch.zeros(1, 2, 3, 4))
+
+
+def test_product_does_not_import_the_oracle():
+    """The product path must never route through the CPU oracle."""
+    pkg = os.path.join(ROOT, "paper_2308_03291_amd")
+    for dirpath, _, files in os.walk(pkg):
+        if "_build" in dirpath:
+            continue
+        for f in files:
+            if f.endswith((".py", ".hip", ".h", ".cpp")):
+                text = open(os.path.join(dirpath, f)).read()
+                assert "import oracle" not in text and "from oracle" not in text, f
+                assert "lccrf_oracle" not in text, f

@@ -1,0 +1,303 @@
+"""GPU parity: the HIP path (through the C ABI) against the CPU oracle, element by element,
+on the same seeded inputs.
+
+Tolerances (fixed by the benchmark spec): logZ relative 1e-5 (absolute 1e-5 when |logZ| < 1);
+marginals absolute 1e-5 for float32 potentials, 1e-4 for bfloat16-stored potentials; Viterbi
+tags identical wherever the oracle's gap between the best and the second-best path exceeds
+1e-3, and otherwise any valid path whose score is within the logZ tolerance of the best.
+"""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+from paper_2308_03291_amd import workloads
+
+pytestmark = pytest.mark.gpu
+
+LOGZ_RTOL = 1e-5
+MU_ATOL = {"f32": 1e-5, "bf16": 1e-4}
+GAP_MIN = 1e-3
+
+
+@pytest.fixture(scope="module")
+def crf():
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    from paper_2308_03291_amd import binding
+    binding.load_library()   # fails loudly if the HIP library was not built
+    return binding
+
+
+def _close_logz(got, want, what=""):
+    got = np.asarray(got, dtype=np.float64)
+    want = np.asarray(want, dtype=np.float64)
+    tol = LOGZ_RTOL * np.maximum(np.abs(want), 1.0)
+    both_ninf = np.isneginf(got) & np.isneginf(want)
+    bad = ~both_ninf & ~(np.abs(got - want) <= tol)
+    assert not bad.any(), f"{what}: logZ/score mismatch at {np.nonzero(bad)[0][:8]}: {got[bad][:4]} vs {want[bad][:4]}"
+
+
+def _path_score(phi64, y, L):
+    if L == 0:
+        return 0.0
+    s = phi64[0, 0, y[0]]
+    for i in range(1, L):
+        s += phi64[i, y[i - 1], y[i]]
+    return float(s)
+
+
+def check_case(crf, oracle_mod, phi_cpu, lens_cpu, *, poison=True, algo=0, what="", queries=("logz", "mu", "vit"),
+               device_phi=None):
+    """Run the requested queries on the GPU and compare everything with the oracle."""
+    B, N, T, _ = phi_cpu.shape
+    kind = "bf16" if phi_cpu.dtype == torch.bfloat16 else "f32"
+    lens_np = None if lens_cpu is None else lens_cpu.numpy()
+    eff = np.full((B,), N) if lens_np is None else np.clip(lens_np, 0, N)
+    dev = torch.device("cuda:0")
+    if device_phi is None:
+        src = phi_cpu
+        if poison and kind == "f32":
+            # nothing outside the chain may be read: fill it with NaN on the device copy only
+            src = phi_cpu.clone()
+            for b in range(B):
+                src[b, eff[b]:] = float("nan")
+                if eff[b] > 0:
+                    src[b, 0, 1:] = float("nan")
+        device_phi = src.to(dev)
+    lens_dev = None if lens_cpu is None else lens_cpu.to(dev)
+
+    if "logz" in queries:
+        out = torch.full((B,), float("nan"), device=dev)
+        crf.lccrf_log_partition(device_phi, lens_dev, out=out, algo=algo)
+        want = oracle_mod.log_partition(phi_cpu, lens_np)
+        _close_logz(out.cpu().numpy(), want, what + " log_partition")
+
+    if "mu" in queries:
+        mu = torch.full((B, N, T, T), float("nan"), device=dev)
+        lz = torch.full((B,), float("nan"), device=dev)
+        crf.lccrf_marginals(device_phi, lens_dev, out=mu, logZ=lz, algo=algo)
+        want_lz, want_mu = oracle_mod.marginals(phi_cpu, lens_np)
+        _close_logz(lz.cpu().numpy(), want_lz, what + " marginals.logZ")
+        got_mu = mu.cpu().numpy().astype(np.float64)
+        assert np.isfinite(got_mu).all(), f"{what}: non-finite marginals"
+        err = np.abs(got_mu - want_mu).max()
+        assert err <= MU_ATOL[kind], f"{what}: max |mu - oracle| = {err:.3e}"
+        for b in range(B):   # exact zeros where no edge exists
+            assert not got_mu[b, eff[b]:].any(), f"{what}: marginals past the length of sequence {b}"
+            if eff[b] > 0:
+                assert not got_mu[b, 0, 1:].any(), f"{what}: rows s>0 of position 0, sequence {b}"
+
+    if "vit" in queries:
+        tags = torch.full((B, N), -7, dtype=torch.int32, device=dev)
+        score = torch.full((B,), float("nan"), device=dev)
+        crf.lccrf_argmax(device_phi, lens_dev, out=tags, score=score, algo=algo)
+        want_score, want_tags, gap = oracle_mod.viterbi(phi_cpu, lens_np)
+        got_tags = tags.cpu().numpy()
+        got_score = score.cpu().numpy().astype(np.float64)
+        _close_logz(got_score, want_score, what + " argmax.score")
+        phi64 = phi_cpu.to(torch.float32).numpy().astype(np.float64)
+        for b in range(B):
+            L = int(eff[b])
+            assert (got_tags[b, L:] == -1).all(), f"{what}: tags past the length of sequence {b}"
+            y = got_tags[b, :L]
+            assert ((y >= 0) & (y < T)).all(), f"{what}: tag out of range in sequence {b}"
+            if gap[b] > GAP_MIN:
+                assert np.array_equal(y, want_tags[b, :L]), \
+                    f"{what}: Viterbi path differs in sequence {b} (gap {gap[b]:.3g})"
+            elif np.isfinite(want_score[b]):
+                s = _path_score(phi64[b], y, L)
+                assert abs(s - want_score[b]) <= LOGZ_RTOL * max(1.0, abs(want_score[b])) + GAP_MIN
+
+
+# ---------------------------------------------------------------------------------------
+# sweeps over small and odd shapes: several tiles, ragged tails, degenerate sizes
+
+SWEEP = []
+for T_ in (1, 2, 3, 5, 16, 17, 32, 48, 64, 100, 128):
+    for N_ in (1, 2, 3, 7, 64, 65):
+        if T_ * T_ * N_ <= 128 * 128 * 7 or (N_ in (64,) and T_ in (16, 32, 48)):
+            SWEEP.append((T_, N_))
+SWEEP += [(128, 65), (100, 64), (64, 65), (17, 65)]
+
+
+@pytest.mark.parametrize("T,N", SWEEP)
+def test_sweep_fp32(crf, oracle_mod, T, N):
+    B = 5
+    phi, _ = workloads.random_case(1000 + 7 * T + N, B, N, T, scale=1.5)
+    lens = torch.tensor([N, 1, max(1, N // 2), 0, max(1, N - 1)], dtype=torch.int32)
+    check_case(crf, oracle_mod, phi, lens, what=f"T={T} N={N}")
+
+
+@pytest.mark.parametrize("T,N", [(16, 40), (17, 9), (48, 33), (5, 8), (128, 6)])
+def test_sweep_bf16(crf, oracle_mod, T, N):
+    phi, _ = workloads.random_case(2000 + T + N, 3, N, T, scale=6.0, dtype="bf16")
+    lens = torch.tensor([N, max(1, N // 3), N - 1 if N > 1 else 1], dtype=torch.int32)
+    check_case(crf, oracle_mod, phi, lens, poison=False, what=f"bf16 T={T} N={N}")
+
+
+@pytest.mark.parametrize("T", [255, 256, 129, 200])
+def test_largest_tag_sets(crf, oracle_mod, T):
+    phi, _ = workloads.random_case(3000 + T, 2, 5, T)
+    lens = torch.tensor([5, 3], dtype=torch.int32)
+    check_case(crf, oracle_mod, phi, lens, what=f"T={T}")
+
+
+def test_lengths_none_means_full(crf, oracle_mod):
+    phi, _ = workloads.random_case(3100, 3, 9, 12)
+    check_case(crf, oracle_mod, phi, None, what="lengths=None")
+
+
+def test_lengths_are_clamped(crf, oracle_mod):
+    phi, _ = workloads.random_case(3101, 4, 6, 8)
+    lens = torch.tensor([-3, 99, 6, 2], dtype=torch.int32)
+    check_case(crf, oracle_mod, phi, lens, poison=True, what="clamped lengths")
+
+
+# ---------------------------------------------------------------------------------------
+# special values
+
+def test_zero_potentials(crf):
+    B, N, T = 3, 50, 24
+    phi = torch.zeros(B, N, T, T, device="cuda:0")
+    lens = torch.tensor([50, 17, 1], dtype=torch.int32, device="cuda:0")
+    lz, mu = crf.lccrf_marginals(phi, lens)
+    want = lens.cpu().numpy() * math.log(T)
+    _close_logz(lz.cpu().numpy(), want, "zero potentials")
+    mu = mu.cpu().numpy()
+    assert np.allclose(mu[0, 1:], 1.0 / T ** 2, atol=1e-7)
+    assert np.allclose(mu[0, 0, 0], 1.0 / T, atol=1e-7)
+    score, tags = crf.lccrf_argmax(phi, lens)
+    assert (score.cpu().numpy() == 0).all()
+    t = tags.cpu().numpy()
+    assert (t[0] == 0).all() and (t[1, :17] == 0).all() and (t[1, 17:] == -1).all()
+
+
+def test_banned_transitions(crf, oracle_mod):
+    phi, _ = workloads.random_case(3200, 3, 7, 6)
+    ninf = float("-inf")
+    phi[0, 2, 1, :] = ninf
+    phi[0, 3, :, 0] = ninf
+    phi[1, 0, 0, 2] = ninf
+    phi[1, 4, :, 1:] = ninf       # only tag 0 allowed at position 4
+    phi[2, 3, :, :] = ninf        # no finite path at all in sequence 2
+    lens = torch.tensor([7, 6, 7], dtype=torch.int32)
+    check_case(crf, oracle_mod, phi, lens, poison=False, what="-inf potentials", queries=("logz", "mu"))
+    # argmax on the feasible sequences only
+    check_case(crf, oracle_mod, phi[:2].contiguous(), lens[:2], poison=False, what="-inf potentials",
+               queries=("vit",))
+
+
+def test_hmm_total_mass_is_one(crf):
+    """Row-stochastic potentials: logZ = 0 up to float32 rounding of the inputs."""
+    g = torch.Generator().manual_seed(77)
+    B, N, T = 2, 300, 20
+    P = torch.rand(B, N, T, T, generator=g, dtype=torch.float64) + 0.05
+    P /= P.sum(dim=3, keepdim=True)
+    phi = P.log().to(torch.float32)
+    lz = crf.lccrf_log_partition(phi.cuda()).cpu().numpy()
+    assert np.abs(lz).max() < 2e-4
+
+
+def test_large_offsets_keep_precision(crf, oracle_mod):
+    """A big constant added to every matrix moves logZ by N * c; marginals must not degrade."""
+    phi, _ = workloads.random_case(3300, 2, 200, 16)
+    phi = phi + 300.0
+    check_case(crf, oracle_mod, phi, None, poison=False, what="offset +300", queries=("logz", "mu"))
+
+
+def test_repeat_runs_are_bit_identical(crf):
+    w = workloads.WORKLOADS["cfg2"]
+    phi = workloads.phi_batch(w).cuda()
+    lens = workloads.lengths(w).cuda()
+    lz1, mu1 = crf.lccrf_marginals(phi, lens)
+    s1, t1 = crf.lccrf_argmax(phi, lens)
+    for _ in range(3):
+        lz2, mu2 = crf.lccrf_marginals(phi, lens)
+        s2, t2 = crf.lccrf_argmax(phi, lens)
+        assert torch.equal(lz1, lz2) and torch.equal(mu1, mu2)
+        assert torch.equal(s1, s2) and torch.equal(t1, t2)
+
+
+def test_dirty_workspace_and_side_stream(crf, oracle_mod):
+    phi, lens = workloads.random_case(3400, 6, 30, 20, ragged=True, min_len=0)
+    dev = torch.device("cuda:0")
+    B, N, T, _ = phi.shape
+    need = max(crf.workspace_bytes(op, B, N, T, 0) for op in (0, 1, 2))
+    ws = torch.full((need,), 0xFF, dtype=torch.uint8, device=dev)   # all-ones bytes: NaN as floats
+    st = torch.cuda.Stream(device=dev)
+    phid, lensd = phi.to(dev), lens.to(dev)
+    torch.cuda.synchronize()
+    with torch.cuda.stream(st):
+        lz, mu = crf.lccrf_marginals(phid, lensd, workspace=ws)
+        ws.fill_(0xFF)
+        score, tags = crf.lccrf_argmax(phid, lensd, workspace=ws)
+    st.synchronize()
+    want_lz, want_mu = oracle_mod.marginals(phi, lens.numpy())
+    _close_logz(lz.cpu().numpy(), want_lz, "side stream")
+    assert np.abs(mu.cpu().numpy() - want_mu).max() <= 1e-5
+    want_score, want_tags, gap = oracle_mod.viterbi(phi, lens.numpy())
+    _close_logz(score.cpu().numpy(), want_score, "side stream score")
+    for b in range(B):
+        if gap[b] > GAP_MIN:
+            assert np.array_equal(tags[b].cpu().numpy(), want_tags[b])
+
+
+# ---------------------------------------------------------------------------------------
+# the named workloads
+
+@pytest.mark.parametrize("key", ["cfg1", "cfg2", "cfg3"])
+def test_named_workloads_full(crf, oracle_mod, key):
+    w = workloads.WORKLOADS[key]
+    phi = workloads.phi_batch(w)
+    lens = workloads.lengths(w)
+    check_case(crf, oracle_mod, phi, lens, what=key)
+
+
+def test_config5_long_peaked_bf16(crf, oracle_mod):
+    w = workloads.WORKLOADS["cfg5"]
+    phi = workloads.phi_batch(w)
+    lens = workloads.lengths(w)
+    check_case(crf, oracle_mod, phi, lens, poison=False, what="cfg5")
+
+
+def test_config4_full_size_sampled(crf, oracle_mod):
+    """The 2.1 GB workload in the launch configuration the benchmark times.  The GPU runs the
+    whole batch; the oracle recomputes a sample of sequences (sequences are independent, so
+    each sampled sequence is checked in full), and sum-to-one is checked on all."""
+    w = workloads.WORKLOADS["cfg4"]
+    dev = torch.device("cuda:0")
+    phi_dev = torch.empty(w.B, w.N, w.T, w.T, dtype=torch.float32, device=dev)
+    workloads.phi_batch(w, out=phi_dev)
+    lens = workloads.lengths(w)
+    lens_dev = lens.to(dev)
+    lz, mu = crf.lccrf_marginals(phi_dev, lens_dev)
+    lz_only = crf.lccrf_log_partition(phi_dev, lens_dev)
+    score, tags = crf.lccrf_argmax(phi_dev, lens_dev)
+    torch.cuda.synchronize()
+    sums = mu.sum(dim=(2, 3)).cpu().numpy()
+    assert np.abs(sums - 1.0).max() < 1e-4
+    assert np.isfinite(lz.cpu().numpy()).all()
+    assert torch.allclose(lz, lz_only, rtol=1e-6, atol=0)
+    for b in (0, 29, 63):
+        phi_b = workloads.phi_sequence(w, b).unsqueeze(0)
+        want_lz, want_mu = oracle_mod.marginals(phi_b, None)
+        _close_logz(lz[b:b + 1].cpu().numpy(), want_lz, f"cfg4 seq {b}")
+        err = np.abs(mu[b].cpu().numpy() - want_mu[0]).max()
+        assert err <= 1e-5, f"cfg4 seq {b}: max |mu - oracle| = {err:.3e}"
+        want_score, want_tags, gap = oracle_mod.viterbi(phi_b, None)
+        _close_logz(score[b:b + 1].cpu().numpy(), want_score, f"cfg4 seq {b} score")
+        if gap[0] > GAP_MIN:
+            assert np.array_equal(tags[b].cpu().numpy(), want_tags[0])
+
+
+def test_paper_benchmark_shape(crf, oracle_mod):
+    """The size the paper times this model on (appendix table of tested sizes): b=128, n=256, 32 tags."""
+    w = workloads.WORKLOADS["paper_lccrf"]
+    phi = workloads.phi_batch(w)
+    pick = [0, 17, 127]
+    dev_phi = phi.cuda()
+    lz, mu = crf.lccrf_marginals(dev_phi)
+    want_lz, want_mu = oracle_mod.marginals(phi[pick].contiguous(), None)
+    _close_logz(lz.cpu().numpy()[pick], want_lz, "paper shape")
+    assert np.abs(mu[pick].cpu().numpy() - want_mu).max() <= 1e-5
