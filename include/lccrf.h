@@ -126,6 +126,19 @@ int lccrf_argmax_algo(const void* phi, lccrf_dtype dt, const int32_t* lengths,
                       int B, int N, int T, float* best_score, int32_t* tags,
                       void* workspace, size_t workspace_bytes, void* stream, lccrf_algo algo);
 
+/*
+ * Instrumentation for benchmarks (not a query of its own): lccrf_marginals_algo with three
+ * caller-created hipEvent_t handles (passed as void*, any may be NULL) recorded on `stream`
+ * before the first kernel, between the two passes of the sequential schedule (after every
+ * matrix has been read once and the half-way vectors are stored; before the pass that
+ * re-reads phi and writes the marginals), and after the last kernel.  Lets a caller time the
+ * passes separately with hipEventElapsedTime.  Same results and errors as lccrf_marginals_algo.
+ */
+int lccrf_marginals_timed(const void* phi, lccrf_dtype dt, const int32_t* lengths,
+                          int B, int N, int T, float* logZ, float* marginals,
+                          void* workspace, size_t workspace_bytes, void* stream, lccrf_algo algo,
+                          void* ev_begin, void* ev_between, void* ev_end);
+
 /* Static, human-readable text for a status code. */
 const char* lccrf_strerror(int code);
 

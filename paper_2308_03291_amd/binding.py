@@ -30,7 +30,7 @@ MAX_T = 256
 EXPORTS = (
     "lccrf_workspace_bytes", "lccrf_log_partition", "lccrf_marginals", "lccrf_argmax",
     "lccrf_log_partition_algo", "lccrf_marginals_algo", "lccrf_argmax_algo",
-    "lccrf_strerror", "lccrf_version",
+    "lccrf_marginals_timed", "lccrf_strerror", "lccrf_version",
 )
 
 _lib = None
@@ -60,7 +60,8 @@ def load_library() -> ctypes.CDLL:
     lib.lccrf_log_partition_algo.argtypes = base + [vp, vp, sz, vp, i]
     lib.lccrf_marginals_algo.argtypes = base + [vp, vp, vp, sz, vp, i]
     lib.lccrf_argmax_algo.argtypes = base + [vp, vp, vp, sz, vp, i]
-    for n in ("lccrf_log_partition", "lccrf_marginals", "lccrf_argmax",
+    lib.lccrf_marginals_timed.argtypes = base + [vp, vp, vp, sz, vp, i, vp, vp, vp]
+    for n in ("lccrf_log_partition", "lccrf_marginals", "lccrf_argmax", "lccrf_marginals_timed",
               "lccrf_log_partition_algo", "lccrf_marginals_algo", "lccrf_argmax_algo", "lccrf_version"):
         getattr(lib, n).restype = i
     lib.lccrf_strerror.argtypes = [i]
@@ -176,3 +177,18 @@ def lccrf_argmax(phi: torch.Tensor, lengths: Optional[torch.Tensor] = None, *,
                                    _stream(phi.device), algo)
     _check(rc, "lccrf_argmax")
     return score, out
+
+
+def lccrf_marginals_timed(phi: torch.Tensor, lengths: Optional[torch.Tensor], out: torch.Tensor,
+                          logZ: torch.Tensor, workspace: torch.Tensor, events, algo: int = ALGO_AUTO) -> None:
+    """``lccrf_marginals`` with three ``torch.cuda.Event(enable_timing=True)`` objects recorded by
+    the library before, between and after its two passes (benchmark instrumentation).  The
+    events must have been recorded once before, so that their HIP handles exist."""
+    lib = load_library()
+    dt, B, N, T = _phi_args(phi)
+    handles = [ctypes.c_void_p(e.cuda_event) for e in events]
+    with torch.cuda.device(phi.device):
+        rc = lib.lccrf_marginals_timed(phi.data_ptr(), dt, _len_ptr(lengths, B, phi.device), B, N, T,
+                                       logZ.data_ptr(), out.data_ptr(), workspace.data_ptr(),
+                                       workspace.numel(), _stream(phi.device), algo, *handles)
+    _check(rc, "lccrf_marginals_timed")

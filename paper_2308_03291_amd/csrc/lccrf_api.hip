@@ -42,7 +42,8 @@ int check_common(const void* phi, int dt, int B, int N, int T, const void* ws, s
 }
 
 int sum_query(int op, const void* phi, int dt, const int32_t* lengths, int B, int N, int T, float* logZ,
-              float* marginals, void* workspace, size_t workspace_bytes, void* stream, int algo) {
+              float* marginals, void* workspace, size_t workspace_bytes, void* stream, int algo,
+              void* ev_begin = nullptr, void* ev_between = nullptr, void* ev_end = nullptr) {
     const size_t need = lccrf_workspace_bytes(op == 0 ? LCCRF_OP_LOGZ : LCCRF_OP_MARGINALS, B, N, T,
                                               (lccrf_dtype)dt);
     const int rc = check_common(phi, dt, B, N, T, workspace, workspace_bytes, need, algo);
@@ -54,11 +55,15 @@ int sum_query(int op, const void* phi, int dt, const int32_t* lengths, int B, in
     if (algo == LCCRF_ALGO_SCAN) return LCCRF_ENOTIMPL;
     const SumWorkspace w = sum_workspace(B, N, T);
     char* base = static_cast<char*>(workspace);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (ev_begin && hipEventRecord(static_cast<hipEvent_t>(ev_begin), st) != hipSuccess) return LCCRF_ELAUNCH;
     const hipError_t e = lccrf::launch_sequential_sum(
         op, dt, phi, lengths, B, N, T, reinterpret_cast<float*>(base + w.ua), reinterpret_cast<float*>(base + w.ub),
-        reinterpret_cast<double*>(base + w.Oa), reinterpret_cast<double*>(base + w.Ob), logZ, marginals,
-        static_cast<hipStream_t>(stream));
-    return e == hipSuccess ? LCCRF_OK : LCCRF_ELAUNCH;
+        reinterpret_cast<double*>(base + w.Oa), reinterpret_cast<double*>(base + w.Ob), logZ, marginals, st,
+        static_cast<hipEvent_t>(ev_between));
+    if (e != hipSuccess) return LCCRF_ELAUNCH;
+    if (ev_end && hipEventRecord(static_cast<hipEvent_t>(ev_end), st) != hipSuccess) return LCCRF_ELAUNCH;
+    return LCCRF_OK;
 }
 
 }  // namespace
@@ -83,6 +88,13 @@ int lccrf_log_partition_algo(const void* phi, lccrf_dtype dt, const int32_t* len
 int lccrf_marginals_algo(const void* phi, lccrf_dtype dt, const int32_t* lengths, int B, int N, int T, float* logZ,
                          float* marginals, void* workspace, size_t workspace_bytes, void* stream, lccrf_algo algo) {
     return sum_query(1, phi, dt, lengths, B, N, T, logZ, marginals, workspace, workspace_bytes, stream, algo);
+}
+
+int lccrf_marginals_timed(const void* phi, lccrf_dtype dt, const int32_t* lengths, int B, int N, int T, float* logZ,
+                          float* marginals, void* workspace, size_t workspace_bytes, void* stream, lccrf_algo algo,
+                          void* ev_begin, void* ev_between, void* ev_end) {
+    return sum_query(1, phi, dt, lengths, B, N, T, logZ, marginals, workspace, workspace_bytes, stream, algo,
+                     ev_begin, ev_between, ev_end);
 }
 
 int lccrf_argmax_algo(const void* phi, lccrf_dtype dt, const int32_t* lengths, int B, int N, int T,

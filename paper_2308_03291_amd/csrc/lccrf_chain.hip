@@ -31,6 +31,7 @@ struct ChainSmem {
     alignas(16) float cm[G::TCAP];              // exact column maxima of the current step
     alignas(16) float rvec[2][G::TCAP];         // un-normalised result vector of a step (double buffered)
     alignas(16) float wmax[2][16];              // per-wave maxima of rvec (normaliser = their maximum)
+    alignas(16) float wtot[2][16];              // per-wave sums of the marginals written by a step
     alignas(16) float red[2][4];                // scratch for the mid-point log-sum-exp
 };
 
@@ -38,6 +39,30 @@ template <typename G>
 __device__ __forceinline__ void smem_init(ChainSmem<G>& sm, int tid) {
     for (int k = tid; k < 2 * G::TCAP; k += G::W) (&sm.rvec[0][0])[k] = LCCRF_NEG_INF;
     if (tid < 32) (&sm.wmax[0][0])[tid] = LCCRF_NEG_INF;
+    if (tid < 32) (&sm.wtot[0][0])[tid] = 0.f;
+}
+
+// 1 / (sum of the marginals the last step produced), 0 if that sum is 0.  The marginals of
+// one position must sum to one; scaling by this factor enforces it locally, so that rounding
+// drift between the forward and the backward offsets (a random walk over thousands of steps
+// in float32) never reaches the output.
+template <typename G>
+__device__ __forceinline__ float read_renorm(const ChainSmem<G>& sm, int buf) {
+    float tot = 0.f;
+#pragma unroll
+    for (int w = 0; w < 16; w += 4) {
+        const float4 q = *reinterpret_cast<const float4*>(&sm.wtot[buf][w]);
+        tot += (q.x + q.y) + (q.z + q.w);
+    }
+    return tot > 0.f ? 1.0f / tot : 0.f;
+}
+
+template <typename G>
+__device__ __forceinline__ void scale_tile(float (&mu)[G::ITEMS][4], float c) {
+#pragma unroll
+    for (int k = 0; k < G::ITEMS; ++k)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) mu[k][j] *= c;
 }
 
 // Normaliser of the vector in rvec[buf]: its maximum (0 if the vector is all -inf).
@@ -109,6 +134,11 @@ __device__ __forceinline__ void fwd_step(ChainSmem<G>& sm, int buf, int tid, int
             ls[j] += e;
             if (WITH_MU) mu[k][j] = e * gm[j];
         }
+    if (WITH_MU) {
+        float tot = (ls[0] * gm[0] + ls[1] * gm[1]) + (ls[2] * gm[2] + ls[3] * gm[3]);
+        tot = xor_sum<1, 64>(tot);
+        if (lane == 0) sm.wtot[buf ^ 1][wave] = tot;
+    }
 #pragma unroll
     for (int j = 0; j < 4; ++j) ls[j] = xor_sum<G::LPR, 64>(ls[j]);
     if (lane < G::LPR)
@@ -134,6 +164,7 @@ __device__ __forceinline__ void bwd_step(ChainSmem<G>& sm, int buf, int tid, int
     constexpr int ITEMS = G::ITEMS;
     const int lane = tid & 63, wave = tid >> 6;
     float wm = LCCRF_NEG_INF;
+    float tot = 0.f;
 #pragma unroll
     for (int k = 0; k < ITEMS; ++k) {
         float y[4];
@@ -152,6 +183,7 @@ __device__ __forceinline__ void bwd_step(ChainSmem<G>& sm, int buf, int tid, int
             const float f = ex2(g + uaK[k]);
 #pragma unroll
             for (int j = 0; j < 4; ++j) mu[k][j] = e[j] * f;
+            tot += S * f;  // every lane of the row holds the same S: counted once below
         }
         const int s = r0 + k * G::RPP;
         if (c4 == 0 && s < T) sm.rvec[buf ^ 1][s] = r;
@@ -159,6 +191,10 @@ __device__ __forceinline__ void bwd_step(ChainSmem<G>& sm, int buf, int tid, int
     }
     wm = xor_max<1, 64>(wm);
     if (lane == 0) sm.wmax[buf ^ 1][wave] = wm;
+    if (WITH_MU) {
+        tot = xor_sum<1, 64>(c4 == 0 ? tot : 0.f);
+        if (lane == 0) sm.wtot[buf ^ 1][wave] = tot;
+    }
     __syncthreads();
 }
 
@@ -337,8 +373,16 @@ __global__ __launch_bounds__(G::W) void chain_marginal_kernel(ChainArgs a) {
             for (int j = 0; j < 4; ++j) aux[j] = (c4 + j < T) ? a.ub[(vb + i) * T + c4 + j] : LCCRF_NEG_INF;
             ob = a.Ob[vb + i];
         };
+        int pending = -1;  // position whose marginals wait in registers for their normaliser
+        auto flush = [&]() {
+            if (pending >= 0) {
+                scale_tile<G>(mu, read_renorm<G>(sm, buf));
+                store_tile<G, ALIGNED>(mub + (size_t)pending * TT, T, c4, r0, mu);
+            }
+        };
         auto step = [&](int i, const float (&v)[ITEMS][4], const float (&aux)[4], double ob) {
             const float d = read_shift<G>(sm, buf);
+            flush();
             O += (double)d;
             float ua[ITEMS];
 #pragma unroll
@@ -349,7 +393,7 @@ __global__ __launch_bounds__(G::W) void chain_marginal_kernel(ChainArgs a) {
             const float K = feasible ? (float)(O + ob - lz2) : LCCRF_NEG_INF;
             const float ubK[4] = {aux[0] + K, aux[1] + K, aux[2] + K, aux[3] + K};
             fwd_step<G, true>(sm, buf, tid, c4, v, ua, ubK, mu);
-            store_tile<G, ALIGNED>(mub + (size_t)i * TT, T, c4, r0, mu);
+            pending = i;
             buf ^= 1;
         };
         int i = h + 1;
@@ -362,6 +406,7 @@ __global__ __launch_bounds__(G::W) void chain_marginal_kernel(ChainArgs a) {
             step(i, Bq, auxB, obB);
             ++i;
         }
+        flush();
     } else {
         double O = a.Ob[vb + h];
         publish_columns<G>(sm, 0, tid, (tid < T) ? a.ub[(vb + h) * T + tid] : LCCRF_NEG_INF);
@@ -377,8 +422,16 @@ __global__ __launch_bounds__(G::W) void chain_marginal_kernel(ChainArgs a) {
             }
             oa = a.Oa[vb + i - 1];
         };
+        int pending = -1;
+        auto flush = [&]() {
+            if (pending >= 0) {
+                scale_tile<G>(mu, read_renorm<G>(sm, buf));
+                store_tile<G, ALIGNED>(mub + (size_t)pending * TT, T, c4, r0, mu);
+            }
+        };
         auto step = [&](int i, const float (&v)[ITEMS][4], const float (&aux)[ITEMS], double oa) {
             const float d = read_shift<G>(sm, buf);
+            flush();
             O += (double)d;
             const float4 q = *reinterpret_cast<const float4*>(&sm.rvec[buf][c4]);
             const float ub[4] = {q.x - d, q.y - d, q.z - d, q.w - d};
@@ -387,7 +440,7 @@ __global__ __launch_bounds__(G::W) void chain_marginal_kernel(ChainArgs a) {
 #pragma unroll
             for (int k = 0; k < ITEMS; ++k) uaK[k] = aux[k] + K;
             bwd_step<G, true>(sm, buf, tid, c4, r0, T, v, ub, uaK, mu);
-            store_tile<G, ALIGNED>(mub + (size_t)i * TT, T, c4, r0, mu);
+            pending = i;
             buf ^= 1;
         };
         int i = h;
@@ -400,14 +453,19 @@ __global__ __launch_bounds__(G::W) void chain_marginal_kernel(ChainArgs a) {
             step(i, Bq, auxB, oaB);
             --i;
         }
-        // position 0: p(y_0 = t) in row 0, zeros in the other rows
-        const float d = read_shift<G>(sm, buf);
-        O += (double)d;
-        const float K = feasible ? (float)(a.Oa[vb] + O - lz2) : LCCRF_NEG_INF;
-        for (int k = tid; k < (int)TT; k += G::W) {
-            float val = 0.f;
-            if (k < T) val = ex2(a.ua[vb * T + k] + (sm.rvec[buf][k] - d) + K);
-            mub[k] = val;
+        flush();
+        // position 0: p(y_0 = t) = softmax_t(alpha_0(t) + beta_0(t)) in row 0, zeros elsewhere
+        for (int k = T + tid; k < (int)TT; k += G::W) mub[k] = 0.f;
+        if (tid < 64) {
+            float m = LCCRF_NEG_INF;
+            for (int t = tid; t < T; t += 64) m = fmaxf(m, a.ua[vb * T + t] + sm.rvec[buf][t]);
+            m = xor_max<1, 64>(m);
+            float S = 0.f;
+            for (int t = tid; t < T; t += 64) S += ex2(a.ua[vb * T + t] + sm.rvec[buf][t] - finite_or_zero(m));
+            S = xor_sum<1, 64>(S);
+            const float c = (feasible && S > 0.f) ? 1.0f / S : 0.f;
+            for (int t = tid; t < T; t += 64)
+                mub[t] = c * ex2(a.ua[vb * T + t] + sm.rvec[buf][t] - finite_or_zero(m));
         }
     }
 }
@@ -438,10 +496,14 @@ __global__ __launch_bounds__(64) void logz_combine_kernel(ChainArgs a) {
 // ---------------------------------------------------------------------------------------
 // Host-side dispatch.
 template <typename G, typename TIN, bool ALIGNED>
-static hipError_t launch_geo(int op, const ChainArgs& a, hipStream_t st) {
+static hipError_t launch_geo(int op, const ChainArgs& a, hipStream_t st, hipEvent_t between) {
     hipLaunchKernelGGL((chain_half_kernel<G, TIN, ALIGNED>), dim3(2 * a.B), dim3(G::W), 0, st, a);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
+    if (between) {
+        e = hipEventRecord(between, st);
+        if (e != hipSuccess) return e;
+    }
     if (op == 0) {
         hipLaunchKernelGGL(logz_combine_kernel, dim3(a.B), dim3(64), 0, st, a);
     } else {
@@ -451,26 +513,26 @@ static hipError_t launch_geo(int op, const ChainArgs& a, hipStream_t st) {
 }
 
 template <typename TIN, bool ALIGNED>
-static hipError_t launch_T(int op, const ChainArgs& a, hipStream_t st) {
+static hipError_t launch_T(int op, const ChainArgs& a, hipStream_t st, hipEvent_t between) {
     const int T = a.T;
-    if (T <= 4) return launch_geo<Geo<1, 1, 1>, TIN, ALIGNED>(op, a, st);
-    if (T <= 8) return launch_geo<Geo<2, 1, 1>, TIN, ALIGNED>(op, a, st);
-    if (T <= 16) return launch_geo<Geo<4, 1, 1>, TIN, ALIGNED>(op, a, st);
-    if (T <= 32) return launch_geo<Geo<8, 4, 1>, TIN, ALIGNED>(op, a, st);
-    if (T <= 64) return launch_geo<Geo<16, 4, 4>, TIN, ALIGNED>(op, a, st);
-    if (T <= 128) return launch_geo<Geo<32, 16, 4>, TIN, ALIGNED>(op, a, st);
-    return launch_geo<Geo<64, 16, 16>, TIN, ALIGNED>(op, a, st);
+    if (T <= 4) return launch_geo<Geo<1, 1, 1>, TIN, ALIGNED>(op, a, st, between);
+    if (T <= 8) return launch_geo<Geo<2, 1, 1>, TIN, ALIGNED>(op, a, st, between);
+    if (T <= 16) return launch_geo<Geo<4, 1, 1>, TIN, ALIGNED>(op, a, st, between);
+    if (T <= 32) return launch_geo<Geo<8, 4, 1>, TIN, ALIGNED>(op, a, st, between);
+    if (T <= 64) return launch_geo<Geo<16, 4, 4>, TIN, ALIGNED>(op, a, st, between);
+    if (T <= 128) return launch_geo<Geo<32, 16, 4>, TIN, ALIGNED>(op, a, st, between);
+    return launch_geo<Geo<64, 16, 16>, TIN, ALIGNED>(op, a, st, between);
 }
 
 // op: 0 = logZ only, 1 = marginals (+ logZ).  Workspace pointers already carved by the caller.
 hipError_t launch_sequential_sum(int op, int dtype, const void* phi, const int32_t* lengths, int B, int N, int T,
                                  float* ua, float* ub, double* Oa, double* Ob, float* logZ, float* mu,
-                                 hipStream_t st) {
+                                 hipStream_t st, hipEvent_t between) {
     ChainArgs a{phi, lengths, B, N, T, ua, ub, Oa, Ob, logZ, mu};
     const bool aligned = (T % 4) == 0;
     if (dtype == 0)
-        return aligned ? launch_T<float, true>(op, a, st) : launch_T<float, false>(op, a, st);
-    return aligned ? launch_T<uint16_t, true>(op, a, st) : launch_T<uint16_t, false>(op, a, st);
+        return aligned ? launch_T<float, true>(op, a, st, between) : launch_T<float, false>(op, a, st, between);
+    return aligned ? launch_T<uint16_t, true>(op, a, st, between) : launch_T<uint16_t, false>(op, a, st, between);
 }
 
 }  // namespace lccrf

@@ -10,9 +10,10 @@ namespace lccrf {
 // Sum-product chains, position by position.  op 0: logZ only; op 1: marginals (+ logZ if
 // non-null).  dtype 0: float, 1: bfloat16.  ua/ub: [B][N][T] floats, Oa/Ob: [B][N] doubles of
 // scratch.  Enqueues on `st`; returns the launch status.
+// `between`, if non-null, is recorded on `st` after the first pass.
 hipError_t launch_sequential_sum(int op, int dtype, const void* phi, const int32_t* lengths, int B, int N, int T,
                                  float* ua, float* ub, double* Oa, double* Ob, float* logZ, float* mu,
-                                 hipStream_t st);
+                                 hipStream_t st, hipEvent_t between = nullptr);
 
 // Max-plus chain with back-pointers and back-trace.  bp: [B][N][T] bytes of scratch.
 hipError_t launch_sequential_max(int dtype, const void* phi, const int32_t* lengths, int B, int N, int T,
