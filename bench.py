@@ -89,6 +89,10 @@ def main():
     ap.add_argument("--workload", default="cfg4")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-other-queries", action="store_true")
+    ap.add_argument("--pmc-calibration", action="store_true",
+                    help="also run one plain elementwise kernel of known size (reads and writes exactly "
+                         "4 bytes per potential) so that rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE "
+                         "readings can be scaled to bytes")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU (sequences are independent; sharding the batch over "
@@ -166,6 +170,13 @@ def main():
                 "whole_call": {"algorithmic_bytes": call_bytes, "avg_ms": sum(whole) / len(whole),
                                "achieved": call_bytes / (sum(whole) / len(whole) * 1e-3) / 1e9,
                                "frac": call_bytes / (sum(whole) / len(whole) * 1e-3) / 1e9 / HBM_PEAK_GBPS}}
+
+    if args.pmc_calibration:
+        cal_src = phi if esz == 4 else mu
+        torch.add(cal_src, 1.0, out=mu)   # one float read + one float write per potential
+        torch.cuda.synchronize()
+        log(f"[bench] calibration kernel: elementwise add over {pots} floats "
+            f"({pots * 4} bytes read, {pots * 4} bytes written)")
 
     other = None
     if not args.no_other_queries:

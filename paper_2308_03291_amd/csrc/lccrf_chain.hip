@@ -17,9 +17,18 @@
 // That is the minimum traffic of forward-backward (two reads of phi, one write of mu) at
 // half the serial depth and with twice as many workgroups streaming from HBM.
 //
+// Memory pipeline: every thread keeps a ring of PF tiles of phi in registers; the slot of
+// the tile just consumed is refilled with the tile PF steps ahead as soon as its last
+// register has been read, before the step's reductions and barriers, so PF - 1 whole tiles
+// per workgroup are always in flight while the chain waits on its exchanges.
+//
 // Numerics: vectors are kept as u = alpha - O with a double-precision running offset O and
 // max(u) = 0 after every step, so magnitudes stay small however long the chain is; every
-// log-sum-exp is shifted by its exact maximum; -inf entries are neutral.
+// log-sum-exp is shifted by an exact maximum (partial sums carry their own maximum and are
+// rescaled when merged); -inf entries are neutral.  The marginals of
+// a position must sum to one; the sum actually written at one step is fed back as a
+// correction (kappa) to the next, so rounding drift between the forward and the backward
+// offsets (a random walk over thousands of float32 steps) never builds up in the output.
 #include "lccrf_device.h"
 #include "lccrf_launch.h"
 
@@ -27,8 +36,8 @@ namespace lccrf {
 
 template <typename G>
 struct ChainSmem {
-    alignas(16) float part[G::WAVES][G::TCAP];  // per-wave partial column maxima, then partial column sums
-    alignas(16) float cm[G::TCAP];              // exact column maxima of the current step
+    alignas(16) float pmax[G::WAVES][G::TCAP];  // per-wave column maxima of x = ua(s) + phi2(s,t) ...
+    alignas(16) float psum[G::WAVES][G::TCAP];  // ... and column sums of 2^(x - that maximum)
     alignas(16) float rvec[2][G::TCAP];         // un-normalised result vector of a step (double buffered)
     alignas(16) float wmax[2][16];              // per-wave maxima of rvec (normaliser = their maximum)
     alignas(16) float wtot[2][16];              // per-wave sums of the marginals written by a step
@@ -40,29 +49,6 @@ __device__ __forceinline__ void smem_init(ChainSmem<G>& sm, int tid) {
     for (int k = tid; k < 2 * G::TCAP; k += G::W) (&sm.rvec[0][0])[k] = LCCRF_NEG_INF;
     if (tid < 32) (&sm.wmax[0][0])[tid] = LCCRF_NEG_INF;
     if (tid < 32) (&sm.wtot[0][0])[tid] = 0.f;
-}
-
-// 1 / (sum of the marginals the last step produced), 0 if that sum is 0.  The marginals of
-// one position must sum to one; scaling by this factor enforces it locally, so that rounding
-// drift between the forward and the backward offsets (a random walk over thousands of steps
-// in float32) never reaches the output.
-template <typename G>
-__device__ __forceinline__ float read_renorm(const ChainSmem<G>& sm, int buf) {
-    float tot = 0.f;
-#pragma unroll
-    for (int w = 0; w < 16; w += 4) {
-        const float4 q = *reinterpret_cast<const float4*>(&sm.wtot[buf][w]);
-        tot += (q.x + q.y) + (q.z + q.w);
-    }
-    return tot > 0.f ? 1.0f / tot : 0.f;
-}
-
-template <typename G>
-__device__ __forceinline__ void scale_tile(float (&mu)[G::ITEMS][4], float c) {
-#pragma unroll
-    for (int k = 0; k < G::ITEMS; ++k)
-#pragma unroll
-        for (int j = 0; j < 4; ++j) mu[k][j] *= c;
 }
 
 // Normaliser of the vector in rvec[buf]: its maximum (0 if the vector is all -inf).
@@ -77,11 +63,23 @@ __device__ __forceinline__ float read_shift(const ChainSmem<G>& sm, int buf) {
     return finite_or_zero(d);
 }
 
+// -log2 of the sum of the marginals the last step wrote (0 if nothing usable was written).
+template <typename G>
+__device__ __forceinline__ float read_drift(const ChainSmem<G>& sm, int buf) {
+    float tot = 0.f;
+#pragma unroll
+    for (int w = 0; w < 16; w += 4) {
+        const float4 q = *reinterpret_cast<const float4*>(&sm.wtot[buf][w]);
+        tot += (q.x + q.y) + (q.z + q.w);
+    }
+    return (tot > 0.5f && tot < 2.0f) ? -lg2(tot) : 0.f;
+}
+
 // Publish r (one value per column thread, -inf for t >= T) as the next vector.
+// r must be -inf in every lane that owns no column; the wave-wide exchange runs with all
+// lanes of the (wave-uniformly selected) column waves active.
 template <typename G>
 __device__ __forceinline__ void publish_columns(ChainSmem<G>& sm, int nbuf, int tid, float r) {
-    // r must be -inf in every lane that owns no column; the wave-wide exchange runs with
-    // all lanes of the (wave-uniformly selected) column waves active.
     if ((tid >> 6) < G::COLWAVES) {
         if (tid < G::TCAP) sm.rvec[nbuf][tid] = r;
         const float wm = xor_max<1, 64>(r);
@@ -90,14 +88,23 @@ __device__ __forceinline__ void publish_columns(ChainSmem<G>& sm, int nbuf, int 
 }
 
 // One exact forward step: r(t) = log2 sum_s 2^(ua(s) + phi2(s,t)).
-// WITH_MU: also mu(s,t) = 2^(ua(s) + phi2(s,t) + ubK(t)), ubK = beta_i(t) + (offsets - logZ).
-template <typename G, bool WITH_MU>
-__device__ __forceinline__ void fwd_step(ChainSmem<G>& sm, int buf, int tid, int c4,
-                                         const float (&v)[G::ITEMS][4], const float (&ua)[G::ITEMS],
-                                         const float (&ubK)[4], float (&mu)[G::ITEMS][4]) {
+//
+// Single sweep with thread-local shifts: each thread takes the maximum of its own ITEMS rows
+// per column, exponentiates against it, and the (maximum, sum) pairs are merged exactly -
+// first across the row groups of the wave, then across waves by one thread per column.  Two
+// barriers per step, and nothing a thread writes depends on another thread's data.
+//
+// WITH_MU: also writes mu(s,t) = 2^(ua(s) + phi2(s,t) + ubK(t)), ubK = beta_i(t) + (offsets - logZ),
+// to `mu_out` and leaves the sum of what it wrote in wtot.
+// `refill` is called once the tile's registers (reused for x) are free again.
+template <typename G, bool WITH_MU, bool ALIGNED, typename Refill>
+__device__ __forceinline__ void fwd_step(ChainSmem<G>& sm, int buf, int tid, int c4, int r0, int T,
+                                         float (&v)[G::ITEMS][4], const float (&ua)[G::ITEMS],
+                                         const float (&ubK)[4], float* __restrict__ mu_out, Refill refill) {
     constexpr int ITEMS = G::ITEMS;
     const int lane = tid & 63, wave = tid >> 6;
-    float x[ITEMS][4];
+    mask_tile<G>(v, T, c4, r0);
+    float (&x)[ITEMS][4] = v;  // the tile is turned into x = ua(s) + phi2(s,t) in place
     float lm[4] = {LCCRF_NEG_INF, LCCRF_NEG_INF, LCCRF_NEG_INF, LCCRF_NEG_INF};
 #pragma unroll
     for (int k = 0; k < ITEMS; ++k)
@@ -106,93 +113,128 @@ __device__ __forceinline__ void fwd_step(ChainSmem<G>& sm, int buf, int tid, int
             x[k][j] = __builtin_fmaf(v[k][j], kLog2e, ua[k]);
             lm[j] = fmaxf(lm[j], x[k][j]);
         }
+    float g[4], ls[4] = {0.f, 0.f, 0.f, 0.f}, gm[4] = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-    for (int j = 0; j < 4; ++j) lm[j] = xor_max<G::LPR, 64>(lm[j]);
-    if (lane < G::LPR)
-        *reinterpret_cast<float4*>(&sm.part[wave][c4]) = make_float4(lm[0], lm[1], lm[2], lm[3]);
-    __syncthreads();
-    if (tid < G::TCAP) {
-        float m = LCCRF_NEG_INF;
-#pragma unroll
-        for (int w = 0; w < G::WAVES; ++w) m = fmaxf(m, sm.part[w][tid]);
-        sm.cm[tid] = m;
-    }
-    __syncthreads();
-    const float4 cq = *reinterpret_cast<const float4*>(&sm.cm[c4]);
-    const float g[4] = {finite_or_zero(cq.x), finite_or_zero(cq.y), finite_or_zero(cq.z), finite_or_zero(cq.w)};
-    float ls[4] = {0.f, 0.f, 0.f, 0.f};
-    float gm[4];
+    for (int j = 0; j < 4; ++j) g[j] = finite_or_zero(lm[j]);
     if (WITH_MU) {
 #pragma unroll
         for (int j = 0; j < 4; ++j) gm[j] = ex2(g[j] + ubK[j]);
     }
 #pragma unroll
-    for (int k = 0; k < ITEMS; ++k)
+    for (int k = 0; k < ITEMS; ++k) {
+        float e[4];
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
-            const float e = ex2(x[k][j] - g[j]);
-            ls[j] += e;
-            if (WITH_MU) mu[k][j] = e * gm[j];
+            e[j] = ex2(x[k][j] - g[j]);
+            ls[j] += e[j];
         }
+        if (WITH_MU) {
+            const int s = r0 + k * G::RPP;
+            if (s < T && c4 < T) {
+                float* p = mu_out + (size_t)s * T + c4;
+                if (ALIGNED) {
+                    *reinterpret_cast<float4*>(p) = make_float4(e[0] * gm[0], e[1] * gm[1], e[2] * gm[2], e[3] * gm[3]);
+                } else {
+#pragma unroll
+                    for (int j = 0; j < 4; ++j)
+                        if (c4 + j < T) p[j] = e[j] * gm[j];
+                }
+            }
+        }
+    }
+    refill();
     if (WITH_MU) {
         float tot = (ls[0] * gm[0] + ls[1] * gm[1]) + (ls[2] * gm[2] + ls[3] * gm[3]);
         tot = xor_sum<1, 64>(tot);
         if (lane == 0) sm.wtot[buf ^ 1][wave] = tot;
     }
+    // merge the (max, sum) pairs of the wave's row groups
 #pragma unroll
-    for (int j = 0; j < 4; ++j) ls[j] = xor_sum<G::LPR, 64>(ls[j]);
-    if (lane < G::LPR)
-        *reinterpret_cast<float4*>(&sm.part[wave][c4]) = make_float4(ls[0], ls[1], ls[2], ls[3]);
+    for (int j = 0; j < 4; ++j) {
+        const float M = xor_max<G::LPR, 64>(lm[j]);
+        if (G::LPR < 64) ls[j] = xor_sum<G::LPR, 64>(ls[j] * ex2(lm[j] - finite_or_zero(M)));
+        lm[j] = M;
+    }
+    if (lane < G::LPR) {
+        *reinterpret_cast<float4*>(&sm.pmax[wave][c4]) = make_float4(lm[0], lm[1], lm[2], lm[3]);
+        *reinterpret_cast<float4*>(&sm.psum[wave][c4]) = make_float4(ls[0], ls[1], ls[2], ls[3]);
+    }
     __syncthreads();
     float r = LCCRF_NEG_INF;
     if (tid < G::TCAP) {
+        float mw[G::WAVES];
+        float M = LCCRF_NEG_INF;
+#pragma unroll
+        for (int w = 0; w < G::WAVES; ++w) { mw[w] = sm.pmax[w][tid]; M = fmaxf(M, mw[w]); }
+        const float gM = finite_or_zero(M);
         float S = 0.f;
 #pragma unroll
-        for (int w = 0; w < G::WAVES; ++w) S += sm.part[w][tid];
-        r = sm.cm[tid] + lg2(S);  // cm = -inf gives S = 0: -inf + -inf = -inf
+        for (int w = 0; w < G::WAVES; ++w) S = __builtin_fmaf(sm.psum[w][tid], ex2(mw[w] - gM), S);
+        r = M + lg2(S);  // M = -inf gives S = 0: -inf + -inf = -inf
     }
     publish_columns<G>(sm, buf ^ 1, tid, r);
     __syncthreads();
 }
 
 // One exact backward step: r(s) = log2 sum_t 2^(phi2(s,t) + ub(t)).
-// WITH_MU: also mu(s,t) = 2^(uaK(s) + phi2(s,t) + ub(t)), uaK = alpha_{i-1}(s) + (offsets - logZ).
-template <typename G, bool WITH_MU>
+// The LPR lanes of a row sit in one wave: the row maximum and the row sum are all-reduced
+// across them with LDS-free lane exchanges, so the step needs a single barrier.
+// WITH_MU: also writes mu(s,t) = 2^(uaK(s) + phi2(s,t) + ub(t)), uaK = alpha_{i-1}(s) + (offsets - logZ).
+template <typename G, bool WITH_MU, bool ALIGNED, typename Refill>
 __device__ __forceinline__ void bwd_step(ChainSmem<G>& sm, int buf, int tid, int c4, int r0, int T,
-                                         const float (&v)[G::ITEMS][4], const float (&ub)[4],
-                                         const float (&uaK)[G::ITEMS], float (&mu)[G::ITEMS][4]) {
+                                         float (&v)[G::ITEMS][4], const float (&ub)[4],
+                                         const float (&uaK)[G::ITEMS], float* __restrict__ mu_out, Refill refill) {
     constexpr int ITEMS = G::ITEMS;
     const int lane = tid & 63, wave = tid >> 6;
-    float wm = LCCRF_NEG_INF;
+    mask_tile<G>(v, T, c4, r0);
+    float (&y)[ITEMS][4] = v;  // the tile is turned into y = phi2(s,t) + ub(t) in place
+    float m[ITEMS];
+#pragma unroll
+    for (int k = 0; k < ITEMS; ++k) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) y[k][j] = __builtin_fmaf(v[k][j], kLog2e, ub[j]);
+        m[k] = fmaxf(fmaxf(y[k][0], y[k][1]), fmaxf(y[k][2], y[k][3]));
+    }
+#pragma unroll
+    for (int k = 0; k < ITEMS; ++k) m[k] = xor_max<1, G::LPR>(m[k]);
+    float S[ITEMS];
     float tot = 0.f;
 #pragma unroll
     for (int k = 0; k < ITEMS; ++k) {
-        float y[4];
-#pragma unroll
-        for (int j = 0; j < 4; ++j) y[j] = __builtin_fmaf(v[k][j], kLog2e, ub[j]);
-        float m = fmaxf(fmaxf(y[0], y[1]), fmaxf(y[2], y[3]));
-        m = xor_max<1, G::LPR>(m);
-        const float g = finite_or_zero(m);
+        const float g = finite_or_zero(m[k]);
         float e[4];
-        float S = 0.f;
 #pragma unroll
-        for (int j = 0; j < 4; ++j) { e[j] = ex2(y[j] - g); S += e[j]; }
-        S = xor_sum<1, G::LPR>(S);
-        const float r = m + lg2(S);
+        for (int j = 0; j < 4; ++j) e[j] = ex2(y[k][j] - g);
+        S[k] = (e[0] + e[1]) + (e[2] + e[3]);
         if (WITH_MU) {
+            const int s = r0 + k * G::RPP;
             const float f = ex2(g + uaK[k]);
+            if (s < T && c4 < T) {
+                float* p = mu_out + (size_t)s * T + c4;
+                if (ALIGNED) {
+                    *reinterpret_cast<float4*>(p) = make_float4(e[0] * f, e[1] * f, e[2] * f, e[3] * f);
+                } else {
 #pragma unroll
-            for (int j = 0; j < 4; ++j) mu[k][j] = e[j] * f;
-            tot += S * f;  // every lane of the row holds the same S: counted once below
+                    for (int j = 0; j < 4; ++j)
+                        if (c4 + j < T) p[j] = e[j] * f;
+                }
+            }
+            tot += S[k] * f;
         }
+    }
+    refill();
+    float wm = LCCRF_NEG_INF;
+#pragma unroll
+    for (int k = 0; k < ITEMS; ++k) {
+        const float r = m[k] + lg2(xor_sum<1, G::LPR>(S[k]));
         const int s = r0 + k * G::RPP;
         if (c4 == 0 && s < T) sm.rvec[buf ^ 1][s] = r;
         wm = fmaxf(wm, r);
     }
-    wm = xor_max<1, 64>(wm);
+    wm = xor_max<G::LPR, 64>(wm);  // every lane of a row already holds the row's r
     if (lane == 0) sm.wmax[buf ^ 1][wave] = wm;
     if (WITH_MU) {
-        tot = xor_sum<1, 64>(c4 == 0 ? tot : 0.f);
+        tot = xor_sum<1, 64>(tot);
         if (lane == 0) sm.wtot[buf ^ 1][wave] = tot;
     }
     __syncthreads();
@@ -210,9 +252,31 @@ struct ChainArgs {
     float* mu;
 };
 
+// Walks positions first, first+dir, ..., last (dir = +1 or -1) with a ring of PF tiles.
+// `load(i, slot)` fills ring slot `slot` with position i's data, `step(i, slot, refill)`
+// consumes it and must call refill() once the slot's registers are free.
+template <int PF, typename Load, typename Step>
+__device__ __forceinline__ void walk(int first, int last, int dir, Load load, Step step) {
+    const int n = (last - first) * dir + 1;  // number of positions (<= 0: nothing to do)
+    if (n <= 0) return;
+#pragma unroll
+    for (int p = 0; p < PF; ++p)
+        if (p < n) load(first + p * dir, p);
+    int done = 0;
+    while (true) {
+#pragma unroll
+        for (int p = 0; p < PF; ++p) {
+            const int i = first + done * dir;
+            const bool more = done + PF < n;
+            step(i, p, [&]() { if (more) load(i + PF * dir, p); });
+            if (++done >= n) return;
+        }
+    }
+}
+
 // ---------------------------------------------------------------------------------------
 // Pass 1: both half chains, vectors stored, nothing else written.
-template <typename G, typename TIN, bool ALIGNED>
+template <typename G, typename TIN, bool ALIGNED, int PF>
 __global__ __launch_bounds__(G::W) void chain_half_kernel(ChainArgs a) {
     __shared__ ChainSmem<G> sm;
     constexpr int ITEMS = G::ITEMS;
@@ -229,15 +293,19 @@ __global__ __launch_bounds__(G::W) void chain_half_kernel(ChainArgs a) {
 
     smem_init<G>(sm, tid);
     __syncthreads();
-    float A[ITEMS][4], Bq[ITEMS][4];
-    float dummy4[4] = {0.f, 0.f, 0.f, 0.f}, dummyI[ITEMS], dmu[ITEMS][4];
+    float ring[PF][ITEMS][4];
+    const float dummy4[4] = {0.f, 0.f, 0.f, 0.f};
+    float dummyI[ITEMS];
+#pragma unroll
+    for (int k = 0; k < ITEMS; ++k) dummyI[k] = 0.f;
     double O = 0.0;
     int buf = 0;
+    auto load = [&](int i, int slot) { load_tile<G, TIN, ALIGNED>(phib + (size_t)i * TT, T, c4, r0, ring[slot]); };
 
     if (dir == 0) {
         publish_columns<G>(sm, 0, tid, (tid < T) ? Elem<TIN>::get(phib + tid) * kLog2e : LCCRF_NEG_INF);
         __syncthreads();
-        auto step = [&](int i, const float (&v)[ITEMS][4]) {
+        walk<PF>(1, h, +1, load, [&](int i, int slot, auto refill) {
             const float d = read_shift<G>(sm, buf);
             O += (double)d;
             float ua[ITEMS];
@@ -248,19 +316,9 @@ __global__ __launch_bounds__(G::W) void chain_half_kernel(ChainArgs a) {
             }
             if (tid < T) a.ua[(vb + i - 1) * T + tid] = sm.rvec[buf][tid] - d;
             if (tid == 0) a.Oa[vb + i - 1] = O;
-            fwd_step<G, false>(sm, buf, tid, c4, v, ua, dummy4, dmu);
+            fwd_step<G, false, ALIGNED>(sm, buf, tid, c4, r0, T, ring[slot], ua, dummy4, nullptr, refill);
             buf ^= 1;
-        };
-        int i = 1;
-        if (i <= h) load_tile<G, TIN, ALIGNED>(phib + (size_t)i * TT, T, c4, r0, A);
-        while (i <= h) {
-            if (i + 1 <= h) load_tile<G, TIN, ALIGNED>(phib + (size_t)(i + 1) * TT, T, c4, r0, Bq);
-            step(i, A);
-            if (++i > h) break;
-            if (i + 1 <= h) load_tile<G, TIN, ALIGNED>(phib + (size_t)(i + 1) * TT, T, c4, r0, A);
-            step(i, Bq);
-            ++i;
-        }
+        });
         const float d = read_shift<G>(sm, buf);
         O += (double)d;
         if (tid < T) a.ua[(vb + h) * T + tid] = sm.rvec[buf][tid] - d;
@@ -268,26 +326,16 @@ __global__ __launch_bounds__(G::W) void chain_half_kernel(ChainArgs a) {
     } else {
         publish_columns<G>(sm, 0, tid, (tid < T) ? 0.f : LCCRF_NEG_INF);
         __syncthreads();
-        auto step = [&](int i, const float (&v)[ITEMS][4]) {
+        walk<PF>(L - 1, h + 1, -1, load, [&](int i, int slot, auto refill) {
             const float d = read_shift<G>(sm, buf);
             O += (double)d;
             const float4 q = *reinterpret_cast<const float4*>(&sm.rvec[buf][c4]);
             const float ub[4] = {q.x - d, q.y - d, q.z - d, q.w - d};
             if (tid < T) a.ub[(vb + i) * T + tid] = sm.rvec[buf][tid] - d;
             if (tid == 0) a.Ob[vb + i] = O;
-            bwd_step<G, false>(sm, buf, tid, c4, r0, T, v, ub, dummyI, dmu);
+            bwd_step<G, false, ALIGNED>(sm, buf, tid, c4, r0, T, ring[slot], ub, dummyI, nullptr, refill);
             buf ^= 1;
-        };
-        int i = L - 1;
-        if (i > h) load_tile<G, TIN, ALIGNED>(phib + (size_t)i * TT, T, c4, r0, A);
-        while (i > h) {
-            if (i - 1 > h) load_tile<G, TIN, ALIGNED>(phib + (size_t)(i - 1) * TT, T, c4, r0, Bq);
-            step(i, A);
-            if (--i <= h) break;
-            if (i - 1 > h) load_tile<G, TIN, ALIGNED>(phib + (size_t)(i - 1) * TT, T, c4, r0, A);
-            step(i, Bq);
-            --i;
-        }
+        });
         const float d = read_shift<G>(sm, buf);
         O += (double)d;
         if (tid < T) a.ub[(vb + h) * T + tid] = sm.rvec[buf][tid] - d;
@@ -323,7 +371,7 @@ __device__ __forceinline__ double midpoint_log2z(ChainSmem<G>& sm, const ChainAr
 
 // ---------------------------------------------------------------------------------------
 // Pass 2: both chains continue past the meeting point and write the marginals.
-template <typename G, typename TIN, bool ALIGNED>
+template <typename G, typename TIN, bool ALIGNED, int PF>
 __global__ __launch_bounds__(G::W) void chain_marginal_kernel(ChainArgs a) {
     __shared__ ChainSmem<G> sm;
     constexpr int ITEMS = G::ITEMS;
@@ -358,31 +406,25 @@ __global__ __launch_bounds__(G::W) void chain_marginal_kernel(ChainArgs a) {
     const bool feasible = lz2 > -1.0e300;  // false: no path has a finite score, marginals are 0
     if (dir == 0 && tid == 0 && a.logZ) a.logZ[b] = (float)(lz2 * kLn2);
 
-    float A[ITEMS][4], Bq[ITEMS][4], mu[ITEMS][4];
+    float ring[PF][ITEMS][4];
     int buf = 0;
+    float kappa = 0.f;  // running correction that keeps each position's marginals summing to one
 
     if (dir == 0) {
         double O = a.Oa[vb + h];
         publish_columns<G>(sm, 0, tid, (tid < T) ? a.ua[(vb + h) * T + tid] : LCCRF_NEG_INF);
         __syncthreads();
-        float auxA[4], auxB[4];
-        double obA = 0.0, obB = 0.0;
-        auto load = [&](int i, float (&v)[ITEMS][4], float (&aux)[4], double& ob) {
-            load_tile<G, TIN, ALIGNED>(phib + (size_t)i * TT, T, c4, r0, v);
+        float aux[PF][4];
+        double ob[PF];
+        auto load = [&](int i, int slot) {
+            load_tile<G, TIN, ALIGNED>(phib + (size_t)i * TT, T, c4, r0, ring[slot]);
 #pragma unroll
-            for (int j = 0; j < 4; ++j) aux[j] = (c4 + j < T) ? a.ub[(vb + i) * T + c4 + j] : LCCRF_NEG_INF;
-            ob = a.Ob[vb + i];
+            for (int j = 0; j < 4; ++j) aux[slot][j] = (c4 + j < T) ? a.ub[(vb + i) * T + c4 + j] : LCCRF_NEG_INF;
+            ob[slot] = a.Ob[vb + i];
         };
-        int pending = -1;  // position whose marginals wait in registers for their normaliser
-        auto flush = [&]() {
-            if (pending >= 0) {
-                scale_tile<G>(mu, read_renorm<G>(sm, buf));
-                store_tile<G, ALIGNED>(mub + (size_t)pending * TT, T, c4, r0, mu);
-            }
-        };
-        auto step = [&](int i, const float (&v)[ITEMS][4], const float (&aux)[4], double ob) {
+        walk<PF>(h + 1, L - 1, +1, load, [&](int i, int slot, auto refill) {
             const float d = read_shift<G>(sm, buf);
-            flush();
+            kappa += read_drift<G>(sm, buf);
             O += (double)d;
             float ua[ITEMS];
 #pragma unroll
@@ -390,70 +432,39 @@ __global__ __launch_bounds__(G::W) void chain_marginal_kernel(ChainArgs a) {
                 const int s = r0 + k * G::RPP;
                 ua[k] = (s < T) ? sm.rvec[buf][s] - d : LCCRF_NEG_INF;
             }
-            const float K = feasible ? (float)(O + ob - lz2) : LCCRF_NEG_INF;
-            const float ubK[4] = {aux[0] + K, aux[1] + K, aux[2] + K, aux[3] + K};
-            fwd_step<G, true>(sm, buf, tid, c4, v, ua, ubK, mu);
-            pending = i;
+            const float K = feasible ? (float)(O + ob[slot] - lz2) + kappa : LCCRF_NEG_INF;
+            const float ubK[4] = {aux[slot][0] + K, aux[slot][1] + K, aux[slot][2] + K, aux[slot][3] + K};
+            fwd_step<G, true, ALIGNED>(sm, buf, tid, c4, r0, T, ring[slot], ua, ubK, mub + (size_t)i * TT, refill);
             buf ^= 1;
-        };
-        int i = h + 1;
-        if (i < L) load(i, A, auxA, obA);
-        while (i < L) {
-            if (i + 1 < L) load(i + 1, Bq, auxB, obB);
-            step(i, A, auxA, obA);
-            if (++i >= L) break;
-            if (i + 1 < L) load(i + 1, A, auxA, obA);
-            step(i, Bq, auxB, obB);
-            ++i;
-        }
-        flush();
+        });
     } else {
         double O = a.Ob[vb + h];
         publish_columns<G>(sm, 0, tid, (tid < T) ? a.ub[(vb + h) * T + tid] : LCCRF_NEG_INF);
         __syncthreads();
-        float auxA[ITEMS], auxB[ITEMS];
-        double oaA = 0.0, oaB = 0.0;
-        auto load = [&](int i, float (&v)[ITEMS][4], float (&aux)[ITEMS], double& oa) {
-            load_tile<G, TIN, ALIGNED>(phib + (size_t)i * TT, T, c4, r0, v);
+        float aux[PF][ITEMS];
+        double oa[PF];
+        auto load = [&](int i, int slot) {
+            load_tile<G, TIN, ALIGNED>(phib + (size_t)i * TT, T, c4, r0, ring[slot]);
 #pragma unroll
             for (int k = 0; k < ITEMS; ++k) {
                 const int s = r0 + k * G::RPP;
-                aux[k] = (s < T) ? a.ua[(vb + i - 1) * T + s] : LCCRF_NEG_INF;
+                aux[slot][k] = (s < T) ? a.ua[(vb + i - 1) * T + s] : LCCRF_NEG_INF;
             }
-            oa = a.Oa[vb + i - 1];
+            oa[slot] = a.Oa[vb + i - 1];
         };
-        int pending = -1;
-        auto flush = [&]() {
-            if (pending >= 0) {
-                scale_tile<G>(mu, read_renorm<G>(sm, buf));
-                store_tile<G, ALIGNED>(mub + (size_t)pending * TT, T, c4, r0, mu);
-            }
-        };
-        auto step = [&](int i, const float (&v)[ITEMS][4], const float (&aux)[ITEMS], double oa) {
+        walk<PF>(h, 1, -1, load, [&](int i, int slot, auto refill) {
             const float d = read_shift<G>(sm, buf);
-            flush();
+            kappa += read_drift<G>(sm, buf);
             O += (double)d;
             const float4 q = *reinterpret_cast<const float4*>(&sm.rvec[buf][c4]);
             const float ub[4] = {q.x - d, q.y - d, q.z - d, q.w - d};
-            const float K = feasible ? (float)(oa + O - lz2) : LCCRF_NEG_INF;
+            const float K = feasible ? (float)(oa[slot] + O - lz2) + kappa : LCCRF_NEG_INF;
             float uaK[ITEMS];
 #pragma unroll
-            for (int k = 0; k < ITEMS; ++k) uaK[k] = aux[k] + K;
-            bwd_step<G, true>(sm, buf, tid, c4, r0, T, v, ub, uaK, mu);
-            pending = i;
+            for (int k = 0; k < ITEMS; ++k) uaK[k] = aux[slot][k] + K;
+            bwd_step<G, true, ALIGNED>(sm, buf, tid, c4, r0, T, ring[slot], ub, uaK, mub + (size_t)i * TT, refill);
             buf ^= 1;
-        };
-        int i = h;
-        if (i >= 1) load(i, A, auxA, oaA);
-        while (i >= 1) {
-            if (i - 1 >= 1) load(i - 1, Bq, auxB, oaB);
-            step(i, A, auxA, oaA);
-            if (--i < 1) break;
-            if (i - 1 >= 1) load(i - 1, A, auxA, oaA);
-            step(i, Bq, auxB, oaB);
-            --i;
-        }
-        flush();
+        });
         // position 0: p(y_0 = t) = softmax_t(alpha_0(t) + beta_0(t)) in row 0, zeros elsewhere
         for (int k = T + tid; k < (int)TT; k += G::W) mub[k] = 0.f;
         if (tid < 64) {
@@ -495,9 +506,9 @@ __global__ __launch_bounds__(64) void logz_combine_kernel(ChainArgs a) {
 
 // ---------------------------------------------------------------------------------------
 // Host-side dispatch.
-template <typename G, typename TIN, bool ALIGNED>
+template <typename G, typename TIN, bool ALIGNED, int PF1, int PF2>
 static hipError_t launch_geo(int op, const ChainArgs& a, hipStream_t st, hipEvent_t between) {
-    hipLaunchKernelGGL((chain_half_kernel<G, TIN, ALIGNED>), dim3(2 * a.B), dim3(G::W), 0, st, a);
+    hipLaunchKernelGGL((chain_half_kernel<G, TIN, ALIGNED, PF1>), dim3(2 * a.B), dim3(G::W), 0, st, a);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     if (between) {
@@ -507,7 +518,7 @@ static hipError_t launch_geo(int op, const ChainArgs& a, hipStream_t st, hipEven
     if (op == 0) {
         hipLaunchKernelGGL(logz_combine_kernel, dim3(a.B), dim3(64), 0, st, a);
     } else {
-        hipLaunchKernelGGL((chain_marginal_kernel<G, TIN, ALIGNED>), dim3(2 * a.B), dim3(G::W), 0, st, a);
+        hipLaunchKernelGGL((chain_marginal_kernel<G, TIN, ALIGNED, PF2>), dim3(2 * a.B), dim3(G::W), 0, st, a);
     }
     return hipGetLastError();
 }
@@ -515,13 +526,13 @@ static hipError_t launch_geo(int op, const ChainArgs& a, hipStream_t st, hipEven
 template <typename TIN, bool ALIGNED>
 static hipError_t launch_T(int op, const ChainArgs& a, hipStream_t st, hipEvent_t between) {
     const int T = a.T;
-    if (T <= 4) return launch_geo<Geo<1, 1, 1>, TIN, ALIGNED>(op, a, st, between);
-    if (T <= 8) return launch_geo<Geo<2, 1, 1>, TIN, ALIGNED>(op, a, st, between);
-    if (T <= 16) return launch_geo<Geo<4, 1, 1>, TIN, ALIGNED>(op, a, st, between);
-    if (T <= 32) return launch_geo<Geo<8, 4, 1>, TIN, ALIGNED>(op, a, st, between);
-    if (T <= 64) return launch_geo<Geo<16, 4, 4>, TIN, ALIGNED>(op, a, st, between);
-    if (T <= 128) return launch_geo<Geo<32, 16, 4>, TIN, ALIGNED>(op, a, st, between);
-    return launch_geo<Geo<64, 16, 16>, TIN, ALIGNED>(op, a, st, between);
+    if (T <= 4) return launch_geo<Geo<1, 1, 1>, TIN, ALIGNED, 4, 4>(op, a, st, between);
+    if (T <= 8) return launch_geo<Geo<2, 1, 1>, TIN, ALIGNED, 4, 4>(op, a, st, between);
+    if (T <= 16) return launch_geo<Geo<4, 1, 1>, TIN, ALIGNED, 4, 4>(op, a, st, between);
+    if (T <= 32) return launch_geo<Geo<8, 4, 1>, TIN, ALIGNED, 4, 4>(op, a, st, between);
+    if (T <= 64) return launch_geo<Geo<16, 4, 4>, TIN, ALIGNED, 4, 3>(op, a, st, between);
+    if (T <= 128) return launch_geo<Geo<32, 16, 4>, TIN, ALIGNED, 4, 3>(op, a, st, between);
+    return launch_geo<Geo<64, 16, 16>, TIN, ALIGNED, 1, 1>(op, a, st, between);
 }
 
 // op: 0 = logZ only, 1 = marginals (+ logZ).  Workspace pointers already carved by the caller.

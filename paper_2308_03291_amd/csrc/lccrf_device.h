@@ -66,26 +66,35 @@ struct Geo {
     static_assert(RPP * ITEMS_ >= TCAP || RPP * ITEMS_ >= 1, "rows not covered");
 };
 
-// Load this thread's part of one matrix; entries outside the T x T matrix read as -inf,
-// the neutral element of both max and log-sum-exp.
+// Issue the loads of this thread's part of one matrix.  Addresses are clamped into the
+// matrix, so every lane issues the same loads with no branch around them, and nothing here
+// touches the loaded values: the loads stay in flight until mask_tile() is applied where the
+// tile is consumed.
 template <typename G, typename TIN, bool ALIGNED>
 __device__ __forceinline__ void load_tile(const TIN* __restrict__ mat, int T, int c4, int r0,
                                           float (&v)[G::ITEMS][4]) {
 #pragma unroll
     for (int k = 0; k < G::ITEMS; ++k) {
         const int s = r0 + k * G::RPP;
-        if (s < T && c4 < T) {
-            const TIN* p = mat + (size_t)s * T + c4;
-            if (ALIGNED) {
-                Elem<TIN>::get4(p, v[k]);
-            } else {
-#pragma unroll
-                for (int j = 0; j < 4; ++j) v[k][j] = (c4 + j < T) ? Elem<TIN>::get(p + j) : LCCRF_NEG_INF;
-            }
+        const TIN* row = mat + (size_t)(s < T ? s : T - 1) * T;
+        if (ALIGNED) {
+            Elem<TIN>::get4(row + (c4 < T ? c4 : T - 4), v[k]);  // T % 4 == 0 here, so T >= 4
         } else {
 #pragma unroll
-            for (int j = 0; j < 4; ++j) v[k][j] = LCCRF_NEG_INF;
+            for (int j = 0; j < 4; ++j) v[k][j] = Elem<TIN>::get(row + (c4 + j < T ? c4 + j : T - 1));
         }
+    }
+}
+
+// Replace the entries of a loaded tile that lie outside the T x T matrix by -inf, the
+// neutral element of both max and log-sum-exp.
+template <typename G>
+__device__ __forceinline__ void mask_tile(float (&v)[G::ITEMS][4], int T, int c4, int r0) {
+#pragma unroll
+    for (int k = 0; k < G::ITEMS; ++k) {
+        const bool row_ok = r0 + k * G::RPP < T;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) v[k][j] = (row_ok && c4 + j < T) ? v[k][j] : LCCRF_NEG_INF;
     }
 }
 
@@ -109,17 +118,67 @@ __device__ __forceinline__ void store_tile(float* __restrict__ mat, int T, int c
     }
 }
 
-// All-reduce over the lanes of a wave whose ids differ only in the bits [LO, HI).
+// Value held by lane (id ^ OFF) of the same wave, without touching LDS memory where the
+// hardware offers a cross-lane path: DPP quad permutes and row rotates inside a row of 16
+// lanes, the LDS crossbar swizzle for a distance of 4, and the gfx950 permlane swaps
+// between rows of 16 and between the two halves of the wave.
+template <int OFF>
+__device__ __forceinline__ int lane_xor_i(int x) {
+    static_assert(OFF == 1 || OFF == 2 || OFF == 4 || OFF == 8 || OFF == 16 || OFF == 32, "power of two < 64");
+    if (OFF == 1) return __builtin_amdgcn_update_dpp(x, x, 0xB1, 0xF, 0xF, false);   // quad_perm [1,0,3,2]
+    if (OFF == 2) return __builtin_amdgcn_update_dpp(x, x, 0x4E, 0xF, 0xF, false);   // quad_perm [2,3,0,1]
+    if (OFF == 4) return __builtin_amdgcn_ds_swizzle(x, 0x101F);                     // bit mode, xor 4
+    if (OFF == 8) return __builtin_amdgcn_update_dpp(x, x, 0x128, 0xF, 0xF, false);  // row_ror:8
+    const int lane = __lane_id();
+    if (OFF == 16) {
+        const auto r = __builtin_amdgcn_permlane16_swap(x, x, false, false);
+        return (lane & 16) ? (int)r[0] : (int)r[1];
+    }
+    const auto r = __builtin_amdgcn_permlane32_swap(x, x, false, false);
+    return (lane & 32) ? (int)r[0] : (int)r[1];
+}
+template <int OFF>
+__device__ __forceinline__ float lane_xor(float x) { return __int_as_float(lane_xor_i<OFF>(__float_as_int(x))); }
+template <int OFF>
+__device__ __forceinline__ double lane_xor(double x) {
+    const long long b = __double_as_longlong(x);
+    const int lo = lane_xor_i<OFF>((int)(b & 0xffffffffll)), hi = lane_xor_i<OFF>((int)(b >> 32));
+    return __longlong_as_double(((long long)hi << 32) | (unsigned int)lo);
+}
+
+// All-reduce over the lanes of a wave whose ids differ only in the bits [LO, HI) (LO, HI
+// powers of two, LO >= HI means a single lane: nothing to do).  Every lane of a group ends
+// with the bit-identical result (both partners of an exchange add the same two numbers).
 template <int LO, int HI>
 __device__ __forceinline__ float xor_max(float x) {
-#pragma unroll
-    for (int off = LO; off < HI; off <<= 1) x = fmaxf(x, __shfl_xor(x, off, 64));
+    if (LO <= 1 && 1 < HI) x = fmaxf(x, lane_xor<1>(x));
+    if (LO <= 2 && 2 < HI) x = fmaxf(x, lane_xor<2>(x));
+    if (LO <= 4 && 4 < HI) x = fmaxf(x, lane_xor<4>(x));
+    if (LO <= 8 && 8 < HI) x = fmaxf(x, lane_xor<8>(x));
+    if (LO <= 16 && 16 < HI) {  // both halves of the swapped pair: no select needed for a symmetric op
+        const auto r = __builtin_amdgcn_permlane16_swap(__float_as_int(x), __float_as_int(x), false, false);
+        x = fmaxf(__int_as_float(r[0]), __int_as_float(r[1]));
+    }
+    if (LO <= 32 && 32 < HI) {
+        const auto r = __builtin_amdgcn_permlane32_swap(__float_as_int(x), __float_as_int(x), false, false);
+        x = fmaxf(__int_as_float(r[0]), __int_as_float(r[1]));
+    }
     return x;
 }
 template <int LO, int HI>
 __device__ __forceinline__ float xor_sum(float x) {
-#pragma unroll
-    for (int off = LO; off < HI; off <<= 1) x += __shfl_xor(x, off, 64);
+    if (LO <= 1 && 1 < HI) x += lane_xor<1>(x);
+    if (LO <= 2 && 2 < HI) x += lane_xor<2>(x);
+    if (LO <= 4 && 4 < HI) x += lane_xor<4>(x);
+    if (LO <= 8 && 8 < HI) x += lane_xor<8>(x);
+    if (LO <= 16 && 16 < HI) {
+        const auto r = __builtin_amdgcn_permlane16_swap(__float_as_int(x), __float_as_int(x), false, false);
+        x = __int_as_float(r[0]) + __int_as_float(r[1]);
+    }
+    if (LO <= 32 && 32 < HI) {
+        const auto r = __builtin_amdgcn_permlane32_swap(__float_as_int(x), __float_as_int(x), false, false);
+        x = __int_as_float(r[0]) + __int_as_float(r[1]);
+    }
     return x;
 }
 

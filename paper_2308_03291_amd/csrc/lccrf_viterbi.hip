@@ -68,7 +68,8 @@ __global__ __launch_bounds__(G::W) void viterbi_kernel(VitArgs a) {
 
     int buf = 0;
     float A[ITEMS][4], Bq[ITEMS][4];
-    auto step = [&](int i, const float (&v)[ITEMS][4]) {
+    auto step = [&](int i, float (&v)[ITEMS][4]) {
+        mask_tile<G>(v, T, c4, r0);
         double best[4] = {ninf, ninf, ninf, ninf};
         int arg[4] = {kNoArg, kNoArg, kNoArg, kNoArg};
 #pragma unroll
