@@ -56,9 +56,13 @@ typedef enum { LCCRF_OP_LOGZ = 0, LCCRF_OP_MARGINALS = 1, LCCRF_OP_ARGMAX = 2 } 
  * rounding; AUTO picks by shape. */
 typedef enum {
     LCCRF_ALGO_AUTO = 0,
-    LCCRF_ALGO_SEQUENTIAL = 1, /* position by position (the forward algorithm as the paper uses it) */
-    LCCRF_ALGO_SCAN = 2        /* chunked associative scan over positions (the parallel variant the
+    LCCRF_ALGO_SEQUENTIAL = 1, /* position by position (the forward algorithm as the paper uses it), one
+                                  workgroup per chain; AUTO may instead split a chain over two workgroups */
+    LCCRF_ALGO_SCAN = 2,       /* chunked associative scan over positions (the parallel variant the
                                   paper cites in "Sequence Tagging"); only where implemented */
+    LCCRF_ALGO_SEQUENTIAL_EXACT = 3 /* sequential, and every log-sum-exp shifted by its own maximum:
+                                  the step that normally only replays rejected speculative steps
+                                  is used for every position (same results up to rounding; slower) */
 } lccrf_algo;
 
 typedef enum {

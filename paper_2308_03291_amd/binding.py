@@ -24,7 +24,7 @@ LIB_PATH = os.path.join(_HERE, "liblccrf.so")
 
 LCCRF_F32, LCCRF_BF16 = 0, 1
 OP_LOGZ, OP_MARGINALS, OP_ARGMAX = 0, 1, 2
-ALGO_AUTO, ALGO_SEQUENTIAL, ALGO_SCAN = 0, 1, 2
+ALGO_AUTO, ALGO_SEQUENTIAL, ALGO_SCAN, ALGO_SEQUENTIAL_EXACT = 0, 1, 2, 3
 MAX_T = 256
 
 EXPORTS = (

@@ -9,7 +9,7 @@ constexpr size_t kAlign = 256;
 inline size_t round_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 
 struct SumWorkspace {
-    size_t ua, ub, Oa, Ob, total;
+    size_t ua, ub, Oa, Ob, mail, failed, total;
 };
 inline SumWorkspace sum_workspace(size_t B, size_t N, size_t T) {
     SumWorkspace w;
@@ -18,6 +18,8 @@ inline SumWorkspace sum_workspace(size_t B, size_t N, size_t T) {
     w.ub = off; off += round_up(B * N * T * sizeof(float));
     w.Oa = off; off += round_up(B * N * sizeof(double));
     w.Ob = off; off += round_up(B * N * sizeof(double));
+    w.mail = off; off += round_up(lccrf::pair_mail_words((int)B) * sizeof(unsigned long long));
+    w.failed = off; off += round_up(B * sizeof(int));
     w.total = off;
     return w;
 }
@@ -34,7 +36,7 @@ inline bool aligned_to(const void* p, size_t a) { return (reinterpret_cast<uintp
 int check_common(const void* phi, int dt, int B, int N, int T, const void* ws, size_t ws_bytes, size_t need,
                  int algo) {
     if (!shape_ok(B, N, T) || !dtype_ok(dt)) return LCCRF_EINVAL;
-    if (algo != LCCRF_ALGO_AUTO && algo != LCCRF_ALGO_SEQUENTIAL && algo != LCCRF_ALGO_SCAN) return LCCRF_EINVAL;
+    if (algo < LCCRF_ALGO_AUTO || algo > LCCRF_ALGO_SEQUENTIAL_EXACT) return LCCRF_EINVAL;
     if (!phi) return LCCRF_ENULL;
     if (!ws || ws_bytes < need) return LCCRF_EWORKSPACE;
     if (!aligned_to(phi, 16) || !aligned_to(ws, kAlign)) return LCCRF_EALIGN;
@@ -60,7 +62,9 @@ int sum_query(int op, const void* phi, int dt, const int32_t* lengths, int B, in
     const hipError_t e = lccrf::launch_sequential_sum(
         op, dt, phi, lengths, B, N, T, reinterpret_cast<float*>(base + w.ua), reinterpret_cast<float*>(base + w.ub),
         reinterpret_cast<double*>(base + w.Oa), reinterpret_cast<double*>(base + w.Ob), logZ, marginals, st,
-        static_cast<hipEvent_t>(ev_between));
+        static_cast<hipEvent_t>(ev_between), algo == LCCRF_ALGO_SEQUENTIAL_EXACT,
+        algo == LCCRF_ALGO_AUTO ? reinterpret_cast<unsigned long long*>(base + w.mail) : nullptr,
+        reinterpret_cast<int*>(base + w.failed));
     if (e != hipSuccess) return LCCRF_ELAUNCH;
     if (ev_end && hipEventRecord(static_cast<hipEvent_t>(ev_end), st) != hipSuccess) return LCCRF_ELAUNCH;
     return LCCRF_OK;

@@ -23,9 +23,14 @@
 // per workgroup are always in flight while the chain waits on its exchanges.
 //
 // Numerics: vectors are kept as u = alpha - O with a double-precision running offset O and
-// max(u) = 0 after every step, so magnitudes stay small however long the chain is; every
-// log-sum-exp is shifted by an exact maximum (partial sums carry their own maximum and are
-// rescaled when merged); -inf entries are neutral.  The marginals of
+// max(u) = 0 after every step, so magnitudes stay small however long the chain is; -inf
+// entries are neutral.  Every step is first tried with ONE shift for the whole matrix, the
+// previous step's normaliser (potentials of neighbouring positions are on the same scale,
+// so it predicts this step's): one fma, one exp and one add per potential and plain sums to
+// merge.  The step is accepted only if every sum it produced lies in [2^-60, 2^60] - then no
+// term that matters can have overflowed or been flushed - and is otherwise replayed on the
+// same registers by the exact step, whose every log-sum-exp is shifted by its own maximum
+// (partial sums carry their maximum and are rescaled when merged).  The marginals of
 // a position must sum to one; the sum actually written at one step is fed back as a
 // correction (kappa) to the next, so rounding drift between the forward and the backward
 // offsets (a random walk over thousands of float32 steps) never builds up in the output.
@@ -42,6 +47,7 @@ struct ChainSmem {
     alignas(16) float wmax[2][16];              // per-wave maxima of rvec (normaliser = their maximum)
     alignas(16) float wtot[2][16];              // per-wave sums of the marginals written by a step
     alignas(16) float red[2][4];                // scratch for the mid-point log-sum-exp
+    int bad[4];                                 // "speculative step n rejected", indexed by n & 3
 };
 
 template <typename G>
@@ -49,7 +55,11 @@ __device__ __forceinline__ void smem_init(ChainSmem<G>& sm, int tid) {
     for (int k = tid; k < 2 * G::TCAP; k += G::W) (&sm.rvec[0][0])[k] = LCCRF_NEG_INF;
     if (tid < 32) (&sm.wmax[0][0])[tid] = LCCRF_NEG_INF;
     if (tid < 32) (&sm.wtot[0][0])[tid] = 0.f;
+    if (tid < 4) sm.bad[tid] = 0;
 }
+
+constexpr float kSumLo = 0x1p-60f, kSumHi = 0x1p60f;  // accepted range of a speculative sum
+__device__ __forceinline__ bool sum_in_range(float S) { return S >= kSumLo && S <= kSumHi; }  // false for NaN
 
 // Normaliser of the vector in rvec[buf]: its maximum (0 if the vector is all -inf).
 template <typename G>
@@ -87,24 +97,93 @@ __device__ __forceinline__ void publish_columns(ChainSmem<G>& sm, int nbuf, int 
     }
 }
 
-// One exact forward step: r(t) = log2 sum_s 2^(ua(s) + phi2(s,t)).
-//
-// Single sweep with thread-local shifts: each thread takes the maximum of its own ITEMS rows
-// per column, exponentiates against it, and the (maximum, sum) pairs are merged exactly -
-// first across the row groups of the wave, then across waves by one thread per column.  Two
-// barriers per step, and nothing a thread writes depends on another thread's data.
-//
-// WITH_MU: also writes mu(s,t) = 2^(ua(s) + phi2(s,t) + ubK(t)), ubK = beta_i(t) + (offsets - logZ),
-// to `mu_out` and leaves the sum of what it wrote in wtot.
-// `refill` is called once the tile's registers (reused for x) are free again.
-template <typename G, bool WITH_MU, bool ALIGNED, typename Refill>
-__device__ __forceinline__ void fwd_step(ChainSmem<G>& sm, int buf, int tid, int c4, int r0, int T,
-                                         float (&v)[G::ITEMS][4], const float (&ua)[G::ITEMS],
-                                         const float (&ubK)[4], float* __restrict__ mu_out, Refill refill) {
+// Store 4 consecutive marginals of row s (columns c4 .. c4+3), only those inside the matrix.
+template <bool ALIGNED>
+__device__ __forceinline__ void store4(float* __restrict__ mu_out, int T, int s, int c4,
+                                       float a0, float a1, float a2, float a3) {
+    if (s < T && c4 < T) {
+        float* p = mu_out + (size_t)s * T + c4;
+        if (ALIGNED) {
+            *reinterpret_cast<float4*>(p) = make_float4(a0, a1, a2, a3);
+        } else {
+            p[0] = a0;
+            if (c4 + 1 < T) p[1] = a1;
+            if (c4 + 2 < T) p[2] = a2;
+            if (c4 + 3 < T) p[3] = a3;
+        }
+    }
+}
+
+// Tiles arrive with clamped addresses: entries outside the T x T matrix hold finite copies of
+// in-range data.  They never reach a result: rows s >= T carry ua = -inf (forward) or are
+// dropped when the row result is published (backward); columns t >= T carry ub = -inf
+// (backward) or are dropped by the column thread (forward); their marginals are not stored
+// and enter the marginal sum with weight 0.
+
+// ----- forward: r(t) = log2 sum_s 2^(ua(s) + phi2(s,t)) ----------------------------------
+
+// Speculative step with the uniform shift c.  Leaves v untouched.  Sets sm.bad[flag] if a
+// column sum left the accepted range.
+template <typename G, bool WITH_MU, bool ALIGNED>
+__device__ __forceinline__ void fwd_fast(ChainSmem<G>& sm, int buf, int flag, int tid, int c4, int r0, int T,
+                                         const float (&v)[G::ITEMS][4], const float (&ua)[G::ITEMS], float c,
+                                         const float (&ubK)[4], float* __restrict__ mu_out) {
     constexpr int ITEMS = G::ITEMS;
     const int lane = tid & 63, wave = tid >> 6;
-    mask_tile<G>(v, T, c4, r0);
-    float (&x)[ITEMS][4] = v;  // the tile is turned into x = ua(s) + phi2(s,t) in place
+    float ls[4] = {0.f, 0.f, 0.f, 0.f}, gm[4] = {0.f, 0.f, 0.f, 0.f};
+    if (WITH_MU) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) gm[j] = ex2(c + ubK[j]);
+    }
+#pragma unroll
+    for (int k = 0; k < ITEMS; ++k) {
+        const float uac = ua[k] - c;
+        float e[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            e[j] = ex2(__builtin_fmaf(v[k][j], kLog2e, uac));
+            ls[j] += e[j];
+        }
+        if (WITH_MU) store4<ALIGNED>(mu_out, T, r0 + k * G::RPP, c4, e[0] * gm[0], e[1] * gm[1], e[2] * gm[2], e[3] * gm[3]);
+    }
+    if (WITH_MU) {
+        float tot = (ls[0] * gm[0] + ls[1] * gm[1]) + (ls[2] * gm[2] + ls[3] * gm[3]);
+        tot = xor_sum<1, 64>(tot);
+        if (lane == 0) sm.wtot[buf ^ 1][wave] = tot;
+    }
+#pragma unroll
+    for (int j = 0; j < 4; ++j) ls[j] = xor_sum<G::LPR, 64>(ls[j]);
+    if (lane < G::LPR) *reinterpret_cast<float4*>(&sm.psum[wave][c4]) = make_float4(ls[0], ls[1], ls[2], ls[3]);
+    __syncthreads();
+    if (wave < G::COLWAVES) {
+        float r = LCCRF_NEG_INF;
+        bool ok = true;
+        if (tid < T) {
+            float S = 0.f;
+#pragma unroll
+            for (int w = 0; w < G::WAVES; ++w) S += sm.psum[w][tid];
+            r = c + lg2(S);
+            ok = sum_in_range(S);
+        }
+        if (tid < G::TCAP) sm.rvec[buf ^ 1][tid] = r;
+        const float wm = xor_max<1, 64>(r);
+        if (lane == 0) sm.wmax[buf ^ 1][wave] = wm;
+        if (!__all(ok) && lane == 0) sm.bad[flag] = 1;
+    }
+    __syncthreads();
+}
+
+// Exact step: a single sweep with thread-local shifts.  Each thread takes the maximum of its
+// own ITEMS rows per column and exponentiates against it; the (maximum, sum) pairs are merged
+// exactly, first across the row groups of the wave, then across waves by one thread per
+// column.  Turns the tile into x = ua(s) + phi2(s,t) in place.
+template <typename G, bool WITH_MU, bool ALIGNED>
+__device__ __forceinline__ void fwd_exact(ChainSmem<G>& sm, int buf, int tid, int c4, int r0, int T,
+                                          float (&v)[G::ITEMS][4], const float (&ua)[G::ITEMS],
+                                          const float (&ubK)[4], float* __restrict__ mu_out) {
+    constexpr int ITEMS = G::ITEMS;
+    const int lane = tid & 63, wave = tid >> 6;
+    float (&x)[ITEMS][4] = v;
     float lm[4] = {LCCRF_NEG_INF, LCCRF_NEG_INF, LCCRF_NEG_INF, LCCRF_NEG_INF};
 #pragma unroll
     for (int k = 0; k < ITEMS; ++k)
@@ -128,27 +207,13 @@ __device__ __forceinline__ void fwd_step(ChainSmem<G>& sm, int buf, int tid, int
             e[j] = ex2(x[k][j] - g[j]);
             ls[j] += e[j];
         }
-        if (WITH_MU) {
-            const int s = r0 + k * G::RPP;
-            if (s < T && c4 < T) {
-                float* p = mu_out + (size_t)s * T + c4;
-                if (ALIGNED) {
-                    *reinterpret_cast<float4*>(p) = make_float4(e[0] * gm[0], e[1] * gm[1], e[2] * gm[2], e[3] * gm[3]);
-                } else {
-#pragma unroll
-                    for (int j = 0; j < 4; ++j)
-                        if (c4 + j < T) p[j] = e[j] * gm[j];
-                }
-            }
-        }
+        if (WITH_MU) store4<ALIGNED>(mu_out, T, r0 + k * G::RPP, c4, e[0] * gm[0], e[1] * gm[1], e[2] * gm[2], e[3] * gm[3]);
     }
-    refill();
     if (WITH_MU) {
         float tot = (ls[0] * gm[0] + ls[1] * gm[1]) + (ls[2] * gm[2] + ls[3] * gm[3]);
         tot = xor_sum<1, 64>(tot);
         if (lane == 0) sm.wtot[buf ^ 1][wave] = tot;
     }
-    // merge the (max, sum) pairs of the wave's row groups
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
         const float M = xor_max<G::LPR, 64>(lm[j]);
@@ -160,34 +225,81 @@ __device__ __forceinline__ void fwd_step(ChainSmem<G>& sm, int buf, int tid, int
         *reinterpret_cast<float4*>(&sm.psum[wave][c4]) = make_float4(ls[0], ls[1], ls[2], ls[3]);
     }
     __syncthreads();
-    float r = LCCRF_NEG_INF;
-    if (tid < G::TCAP) {
-        float mw[G::WAVES];
-        float M = LCCRF_NEG_INF;
+    if (wave < G::COLWAVES) {
+        float r = LCCRF_NEG_INF;
+        if (tid < T) {
+            float mw[G::WAVES];
+            float M = LCCRF_NEG_INF;
 #pragma unroll
-        for (int w = 0; w < G::WAVES; ++w) { mw[w] = sm.pmax[w][tid]; M = fmaxf(M, mw[w]); }
-        const float gM = finite_or_zero(M);
-        float S = 0.f;
+            for (int w = 0; w < G::WAVES; ++w) { mw[w] = sm.pmax[w][tid]; M = fmaxf(M, mw[w]); }
+            const float gM = finite_or_zero(M);
+            float S = 0.f;
 #pragma unroll
-        for (int w = 0; w < G::WAVES; ++w) S = __builtin_fmaf(sm.psum[w][tid], ex2(mw[w] - gM), S);
-        r = M + lg2(S);  // M = -inf gives S = 0: -inf + -inf = -inf
+            for (int w = 0; w < G::WAVES; ++w) S = __builtin_fmaf(sm.psum[w][tid], ex2(mw[w] - gM), S);
+            r = M + lg2(S);  // M = -inf gives S = 0: -inf + -inf = -inf
+        }
+        if (tid < G::TCAP) sm.rvec[buf ^ 1][tid] = r;
+        const float wm = xor_max<1, 64>(r);
+        if (lane == 0) sm.wmax[buf ^ 1][wave] = wm;
     }
-    publish_columns<G>(sm, buf ^ 1, tid, r);
     __syncthreads();
 }
 
-// One exact backward step: r(s) = log2 sum_t 2^(phi2(s,t) + ub(t)).
-// The LPR lanes of a row sit in one wave: the row maximum and the row sum are all-reduced
-// across them with LDS-free lane exchanges, so the step needs a single barrier.
-// WITH_MU: also writes mu(s,t) = 2^(uaK(s) + phi2(s,t) + ub(t)), uaK = alpha_{i-1}(s) + (offsets - logZ).
-template <typename G, bool WITH_MU, bool ALIGNED, typename Refill>
-__device__ __forceinline__ void bwd_step(ChainSmem<G>& sm, int buf, int tid, int c4, int r0, int T,
-                                         float (&v)[G::ITEMS][4], const float (&ub)[4],
-                                         const float (&uaK)[G::ITEMS], float* __restrict__ mu_out, Refill refill) {
+// ----- backward: r(s) = log2 sum_t 2^(phi2(s,t) + ub(t)) ---------------------------------
+// The LPR lanes of a row sit in one wave: row sums (and, in the exact step, row maxima) are
+// all-reduced across them with LDS-free lane exchanges, so a step needs a single barrier.
+
+template <typename G, bool WITH_MU, bool ALIGNED>
+__device__ __forceinline__ void bwd_fast(ChainSmem<G>& sm, int buf, int flag, int tid, int c4, int r0, int T,
+                                         const float (&v)[G::ITEMS][4], const float (&ub)[4], float c,
+                                         const float (&uaK)[G::ITEMS], float* __restrict__ mu_out) {
     constexpr int ITEMS = G::ITEMS;
     const int lane = tid & 63, wave = tid >> 6;
-    mask_tile<G>(v, T, c4, r0);
-    float (&y)[ITEMS][4] = v;  // the tile is turned into y = phi2(s,t) + ub(t) in place
+    const float ubc[4] = {ub[0] - c, ub[1] - c, ub[2] - c, ub[3] - c};
+    float S[ITEMS];
+    float tot = 0.f;
+#pragma unroll
+    for (int k = 0; k < ITEMS; ++k) {
+        float e[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) e[j] = ex2(__builtin_fmaf(v[k][j], kLog2e, ubc[j]));
+        S[k] = (e[0] + e[1]) + (e[2] + e[3]);
+        if (WITH_MU) {
+            const float f = ex2(c + uaK[k]);
+            store4<ALIGNED>(mu_out, T, r0 + k * G::RPP, c4, e[0] * f, e[1] * f, e[2] * f, e[3] * f);
+            tot += S[k] * f;
+        }
+    }
+    float wm = LCCRF_NEG_INF;
+    bool ok = true;
+#pragma unroll
+    for (int k = 0; k < ITEMS; ++k) {
+        const float Sk = xor_sum<1, G::LPR>(S[k]);
+        const int s = r0 + k * G::RPP;
+        const float r = (s < T) ? c + lg2(Sk) : LCCRF_NEG_INF;
+        if (c4 == 0 && s < T) sm.rvec[buf ^ 1][s] = r;
+        ok = ok && (s >= T || sum_in_range(Sk));
+        wm = fmaxf(wm, r);
+    }
+    wm = xor_max<G::LPR, 64>(wm);  // every lane of a row already holds the row's r
+    if (lane == 0) sm.wmax[buf ^ 1][wave] = wm;
+    if (!__all(ok) && lane == 0) sm.bad[flag] = 1;
+    if (WITH_MU) {
+        tot = xor_sum<1, 64>(tot);
+        if (lane == 0) sm.wtot[buf ^ 1][wave] = tot;
+    }
+    __syncthreads();
+}
+
+// Exact step: row maximum first, then the sum against it.  Turns the tile into
+// y = phi2(s,t) + ub(t) in place.
+template <typename G, bool WITH_MU, bool ALIGNED>
+__device__ __forceinline__ void bwd_exact(ChainSmem<G>& sm, int buf, int tid, int c4, int r0, int T,
+                                          float (&v)[G::ITEMS][4], const float (&ub)[4],
+                                          const float (&uaK)[G::ITEMS], float* __restrict__ mu_out) {
+    constexpr int ITEMS = G::ITEMS;
+    const int lane = tid & 63, wave = tid >> 6;
+    float (&y)[ITEMS][4] = v;
     float m[ITEMS];
 #pragma unroll
     for (int k = 0; k < ITEMS; ++k) {
@@ -207,31 +319,20 @@ __device__ __forceinline__ void bwd_step(ChainSmem<G>& sm, int buf, int tid, int
         for (int j = 0; j < 4; ++j) e[j] = ex2(y[k][j] - g);
         S[k] = (e[0] + e[1]) + (e[2] + e[3]);
         if (WITH_MU) {
-            const int s = r0 + k * G::RPP;
             const float f = ex2(g + uaK[k]);
-            if (s < T && c4 < T) {
-                float* p = mu_out + (size_t)s * T + c4;
-                if (ALIGNED) {
-                    *reinterpret_cast<float4*>(p) = make_float4(e[0] * f, e[1] * f, e[2] * f, e[3] * f);
-                } else {
-#pragma unroll
-                    for (int j = 0; j < 4; ++j)
-                        if (c4 + j < T) p[j] = e[j] * f;
-                }
-            }
+            store4<ALIGNED>(mu_out, T, r0 + k * G::RPP, c4, e[0] * f, e[1] * f, e[2] * f, e[3] * f);
             tot += S[k] * f;
         }
     }
-    refill();
     float wm = LCCRF_NEG_INF;
 #pragma unroll
     for (int k = 0; k < ITEMS; ++k) {
-        const float r = m[k] + lg2(xor_sum<1, G::LPR>(S[k]));
         const int s = r0 + k * G::RPP;
+        const float r = (s < T) ? m[k] + lg2(xor_sum<1, G::LPR>(S[k])) : LCCRF_NEG_INF;
         if (c4 == 0 && s < T) sm.rvec[buf ^ 1][s] = r;
         wm = fmaxf(wm, r);
     }
-    wm = xor_max<G::LPR, 64>(wm);  // every lane of a row already holds the row's r
+    wm = xor_max<G::LPR, 64>(wm);
     if (lane == 0) sm.wmax[buf ^ 1][wave] = wm;
     if (WITH_MU) {
         tot = xor_sum<1, 64>(tot);
@@ -250,28 +351,69 @@ struct ChainArgs {
     double* Ob;  // [B][N] backward offsets
     float* logZ;
     float* mu;
+    int exact_only;  // 1: never take the speculative step (tests)
+    const int* only_failed;  // second pass: if set, recompute only the sequences flagged here
 };
 
-// Walks positions first, first+dir, ..., last (dir = +1 or -1) with a ring of PF tiles.
-// `load(i, slot)` fills ring slot `slot` with position i's data, `step(i, slot, refill)`
-// consumes it and must call refill() once the slot's registers are free.
+// Walks positions first, first+dir, ..., last (dir = +1 or -1) with a ring of PF tiles:
+// `load(i, slot)` issues the loads of position i into ring slot `slot`; `step(i, slot)`
+// consumes the slot, which is refilled with the tile PF positions ahead right after.
+//
+// Every refill is issued unconditionally (past the end of the walk the last position is
+// simply loaded again and never used).  That costs PF redundant tile loads per chain and buys
+// a loop in which the number of loads issued after any tile is the same on every path, which
+// is what lets the compiler wait for exactly the oldest tile (s_waitcnt vmcnt(n) with n > 0)
+// and keep the PF - 1 younger ones in flight.
 template <int PF, typename Load, typename Step>
 __device__ __forceinline__ void walk(int first, int last, int dir, Load load, Step step) {
     const int n = (last - first) * dir + 1;  // number of positions (<= 0: nothing to do)
     if (n <= 0) return;
 #pragma unroll
-    for (int p = 0; p < PF; ++p)
-        if (p < n) load(first + p * dir, p);
+    for (int p = 0; p < PF; ++p) load(first + (p < n ? p : n - 1) * dir, p);
     int done = 0;
     while (true) {
 #pragma unroll
         for (int p = 0; p < PF; ++p) {
             const int i = first + done * dir;
-            const bool more = done + PF < n;
-            step(i, p, [&]() { if (more) load(i + PF * dir, p); });
+            step(i, p);
+            const int ahead = done + PF;
+            load(first + (ahead < n ? ahead : n - 1) * dir, p);
             if (++done >= n) return;
         }
     }
+}
+
+// One position of a forward chain: speculative step, exact replay if it was rejected.
+template <typename G, bool WITH_MU, bool ALIGNED>
+__device__ __forceinline__ void fwd_advance(ChainSmem<G>& sm, int& buf, int& nstep, bool exact_only, int tid, int c4,
+                                            int r0, int T, float (&v)[G::ITEMS][4], const float (&ua)[G::ITEMS],
+                                            float c, const float (&ubK)[4], float* __restrict__ mu_out) {
+    bool replay = exact_only;
+    if (!exact_only) {
+        const int flag = nstep & 3;
+        if (tid == 0) sm.bad[(nstep + 1) & 3] = 0;
+        fwd_fast<G, WITH_MU, ALIGNED>(sm, buf, flag, tid, c4, r0, T, v, ua, c, ubK, mu_out);
+        replay = sm.bad[flag] != 0;
+    }
+    if (replay) fwd_exact<G, WITH_MU, ALIGNED>(sm, buf, tid, c4, r0, T, v, ua, ubK, mu_out);
+    buf ^= 1;
+    ++nstep;
+}
+
+template <typename G, bool WITH_MU, bool ALIGNED>
+__device__ __forceinline__ void bwd_advance(ChainSmem<G>& sm, int& buf, int& nstep, bool exact_only, int tid, int c4,
+                                            int r0, int T, float (&v)[G::ITEMS][4], const float (&ub)[4], float c,
+                                            const float (&uaK)[G::ITEMS], float* __restrict__ mu_out) {
+    bool replay = exact_only;
+    if (!exact_only) {
+        const int flag = nstep & 3;
+        if (tid == 0) sm.bad[(nstep + 1) & 3] = 0;
+        bwd_fast<G, WITH_MU, ALIGNED>(sm, buf, flag, tid, c4, r0, T, v, ub, c, uaK, mu_out);
+        replay = sm.bad[flag] != 0;
+    }
+    if (replay) bwd_exact<G, WITH_MU, ALIGNED>(sm, buf, tid, c4, r0, T, v, ub, uaK, mu_out);
+    buf ^= 1;
+    ++nstep;
 }
 
 // ---------------------------------------------------------------------------------------
@@ -290,6 +432,7 @@ __global__ __launch_bounds__(G::W) void chain_half_kernel(ChainArgs a) {
     const TIN* phib = static_cast<const TIN*>(a.phi) + (size_t)b * N * T * T;
     const size_t TT = (size_t)T * T;
     const size_t vb = (size_t)b * N;
+    const bool exact_only = a.exact_only != 0;
 
     smem_init<G>(sm, tid);
     __syncthreads();
@@ -299,13 +442,13 @@ __global__ __launch_bounds__(G::W) void chain_half_kernel(ChainArgs a) {
 #pragma unroll
     for (int k = 0; k < ITEMS; ++k) dummyI[k] = 0.f;
     double O = 0.0;
-    int buf = 0;
+    int buf = 0, nstep = 0;
     auto load = [&](int i, int slot) { load_tile<G, TIN, ALIGNED>(phib + (size_t)i * TT, T, c4, r0, ring[slot]); };
 
     if (dir == 0) {
         publish_columns<G>(sm, 0, tid, (tid < T) ? Elem<TIN>::get(phib + tid) * kLog2e : LCCRF_NEG_INF);
         __syncthreads();
-        walk<PF>(1, h, +1, load, [&](int i, int slot, auto refill) {
+        walk<PF>(1, h, +1, load, [&](int i, int slot) {
             const float d = read_shift<G>(sm, buf);
             O += (double)d;
             float ua[ITEMS];
@@ -316,8 +459,7 @@ __global__ __launch_bounds__(G::W) void chain_half_kernel(ChainArgs a) {
             }
             if (tid < T) a.ua[(vb + i - 1) * T + tid] = sm.rvec[buf][tid] - d;
             if (tid == 0) a.Oa[vb + i - 1] = O;
-            fwd_step<G, false, ALIGNED>(sm, buf, tid, c4, r0, T, ring[slot], ua, dummy4, nullptr, refill);
-            buf ^= 1;
+            fwd_advance<G, false, ALIGNED>(sm, buf, nstep, exact_only, tid, c4, r0, T, ring[slot], ua, d, dummy4, nullptr);
         });
         const float d = read_shift<G>(sm, buf);
         O += (double)d;
@@ -326,15 +468,14 @@ __global__ __launch_bounds__(G::W) void chain_half_kernel(ChainArgs a) {
     } else {
         publish_columns<G>(sm, 0, tid, (tid < T) ? 0.f : LCCRF_NEG_INF);
         __syncthreads();
-        walk<PF>(L - 1, h + 1, -1, load, [&](int i, int slot, auto refill) {
+        walk<PF>(L - 1, h + 1, -1, load, [&](int i, int slot) {
             const float d = read_shift<G>(sm, buf);
             O += (double)d;
             const float4 q = *reinterpret_cast<const float4*>(&sm.rvec[buf][c4]);
             const float ub[4] = {q.x - d, q.y - d, q.z - d, q.w - d};
             if (tid < T) a.ub[(vb + i) * T + tid] = sm.rvec[buf][tid] - d;
             if (tid == 0) a.Ob[vb + i] = O;
-            bwd_step<G, false, ALIGNED>(sm, buf, tid, c4, r0, T, ring[slot], ub, dummyI, nullptr, refill);
-            buf ^= 1;
+            bwd_advance<G, false, ALIGNED>(sm, buf, nstep, exact_only, tid, c4, r0, T, ring[slot], ub, d, dummyI, nullptr);
         });
         const float d = read_shift<G>(sm, buf);
         O += (double)d;
@@ -382,6 +523,8 @@ __global__ __launch_bounds__(G::W) void chain_marginal_kernel(ChainArgs a) {
     const size_t TT = (size_t)T * T;
     const size_t vb = (size_t)b * N;
     float* mub = a.mu + (size_t)b * N * TT;
+    const bool exact_only = a.exact_only != 0;
+    if (a.only_failed && a.only_failed[b] == 0) return;  // the paired pass has done this sequence
 
     if (dir == 0) {
         // positions past the end carry no edge: their marginals are zero
@@ -407,7 +550,7 @@ __global__ __launch_bounds__(G::W) void chain_marginal_kernel(ChainArgs a) {
     if (dir == 0 && tid == 0 && a.logZ) a.logZ[b] = (float)(lz2 * kLn2);
 
     float ring[PF][ITEMS][4];
-    int buf = 0;
+    int buf = 0, nstep = 0;
     float kappa = 0.f;  // running correction that keeps each position's marginals summing to one
 
     if (dir == 0) {
@@ -419,10 +562,10 @@ __global__ __launch_bounds__(G::W) void chain_marginal_kernel(ChainArgs a) {
         auto load = [&](int i, int slot) {
             load_tile<G, TIN, ALIGNED>(phib + (size_t)i * TT, T, c4, r0, ring[slot]);
 #pragma unroll
-            for (int j = 0; j < 4; ++j) aux[slot][j] = (c4 + j < T) ? a.ub[(vb + i) * T + c4 + j] : LCCRF_NEG_INF;
+            for (int j = 0; j < 4; ++j) aux[slot][j] = a.ub[(vb + i) * T + (c4 + j < T ? c4 + j : T - 1)];
             ob[slot] = a.Ob[vb + i];
         };
-        walk<PF>(h + 1, L - 1, +1, load, [&](int i, int slot, auto refill) {
+        walk<PF>(h + 1, L - 1, +1, load, [&](int i, int slot) {
             const float d = read_shift<G>(sm, buf);
             kappa += read_drift<G>(sm, buf);
             O += (double)d;
@@ -433,9 +576,11 @@ __global__ __launch_bounds__(G::W) void chain_marginal_kernel(ChainArgs a) {
                 ua[k] = (s < T) ? sm.rvec[buf][s] - d : LCCRF_NEG_INF;
             }
             const float K = feasible ? (float)(O + ob[slot] - lz2) + kappa : LCCRF_NEG_INF;
-            const float ubK[4] = {aux[slot][0] + K, aux[slot][1] + K, aux[slot][2] + K, aux[slot][3] + K};
-            fwd_step<G, true, ALIGNED>(sm, buf, tid, c4, r0, T, ring[slot], ua, ubK, mub + (size_t)i * TT, refill);
-            buf ^= 1;
+            float ubK[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) ubK[j] = (c4 + j < T) ? aux[slot][j] + K : LCCRF_NEG_INF;
+            fwd_advance<G, true, ALIGNED>(sm, buf, nstep, exact_only, tid, c4, r0, T, ring[slot], ua, d, ubK,
+                                          mub + (size_t)i * TT);
         });
     } else {
         double O = a.Ob[vb + h];
@@ -448,11 +593,11 @@ __global__ __launch_bounds__(G::W) void chain_marginal_kernel(ChainArgs a) {
 #pragma unroll
             for (int k = 0; k < ITEMS; ++k) {
                 const int s = r0 + k * G::RPP;
-                aux[slot][k] = (s < T) ? a.ua[(vb + i - 1) * T + s] : LCCRF_NEG_INF;
+                aux[slot][k] = a.ua[(vb + i - 1) * T + (s < T ? s : T - 1)];
             }
             oa[slot] = a.Oa[vb + i - 1];
         };
-        walk<PF>(h, 1, -1, load, [&](int i, int slot, auto refill) {
+        walk<PF>(h, 1, -1, load, [&](int i, int slot) {
             const float d = read_shift<G>(sm, buf);
             kappa += read_drift<G>(sm, buf);
             O += (double)d;
@@ -461,9 +606,9 @@ __global__ __launch_bounds__(G::W) void chain_marginal_kernel(ChainArgs a) {
             const float K = feasible ? (float)(oa[slot] + O - lz2) + kappa : LCCRF_NEG_INF;
             float uaK[ITEMS];
 #pragma unroll
-            for (int k = 0; k < ITEMS; ++k) uaK[k] = aux[slot][k] + K;
-            bwd_step<G, true, ALIGNED>(sm, buf, tid, c4, r0, T, ring[slot], ub, uaK, mub + (size_t)i * TT, refill);
-            buf ^= 1;
+            for (int k = 0; k < ITEMS; ++k) uaK[k] = (r0 + k * G::RPP < T) ? aux[slot][k] + K : LCCRF_NEG_INF;
+            bwd_advance<G, true, ALIGNED>(sm, buf, nstep, exact_only, tid, c4, r0, T, ring[slot], ub, d, uaK,
+                                          mub + (size_t)i * TT);
         });
         // position 0: p(y_0 = t) = softmax_t(alpha_0(t) + beta_0(t)) in row 0, zeros elsewhere
         for (int k = T + tid; k < (int)TT; k += G::W) mub[k] = 0.f;
@@ -506,8 +651,14 @@ __global__ __launch_bounds__(64) void logz_combine_kernel(ChainArgs a) {
 
 // ---------------------------------------------------------------------------------------
 // Host-side dispatch.
+struct PairPlan {
+    unsigned long long* mail;
+    int* failed;
+    int dtype;
+};
+
 template <typename G, typename TIN, bool ALIGNED, int PF1, int PF2>
-static hipError_t launch_geo(int op, const ChainArgs& a, hipStream_t st, hipEvent_t between) {
+static hipError_t launch_geo(int op, ChainArgs a, hipStream_t st, hipEvent_t between, const PairPlan& pair) {
     hipLaunchKernelGGL((chain_half_kernel<G, TIN, ALIGNED, PF1>), dim3(2 * a.B), dim3(G::W), 0, st, a);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
@@ -517,33 +668,52 @@ static hipError_t launch_geo(int op, const ChainArgs& a, hipStream_t st, hipEven
     }
     if (op == 0) {
         hipLaunchKernelGGL(logz_combine_kernel, dim3(a.B), dim3(64), 0, st, a);
-    } else {
-        hipLaunchKernelGGL((chain_marginal_kernel<G, TIN, ALIGNED, PF2>), dim3(2 * a.B), dim3(G::W), 0, st, a);
+        return hipGetLastError();
     }
+    if (pair.mail) {
+        // two workgroups per chain, speculative steps only; whatever they flag as failed is redone below
+        e = launch_pair_reset(pair.mail, a.B, pair.failed, st);
+        if (e != hipSuccess) return e;
+        e = launch_pair_marginals(pair.dtype, a.phi, a.lengths, a.B, a.N, a.T, a.ua, a.ub, a.Oa, a.Ob, a.logZ, a.mu,
+                                  pair.mail, pair.failed, st);
+        if (e != hipSuccess) return e;
+        a.only_failed = pair.failed;
+    }
+    hipLaunchKernelGGL((chain_marginal_kernel<G, TIN, ALIGNED, PF2>), dim3(2 * a.B), dim3(G::W), 0, st, a);
     return hipGetLastError();
 }
 
 template <typename TIN, bool ALIGNED>
-static hipError_t launch_T(int op, const ChainArgs& a, hipStream_t st, hipEvent_t between) {
+static hipError_t launch_T(int op, const ChainArgs& a, hipStream_t st, hipEvent_t between, const PairPlan& pair) {
     const int T = a.T;
-    if (T <= 4) return launch_geo<Geo<1, 1, 1>, TIN, ALIGNED, 4, 4>(op, a, st, between);
-    if (T <= 8) return launch_geo<Geo<2, 1, 1>, TIN, ALIGNED, 4, 4>(op, a, st, between);
-    if (T <= 16) return launch_geo<Geo<4, 1, 1>, TIN, ALIGNED, 4, 4>(op, a, st, between);
-    if (T <= 32) return launch_geo<Geo<8, 4, 1>, TIN, ALIGNED, 4, 4>(op, a, st, between);
-    if (T <= 64) return launch_geo<Geo<16, 4, 4>, TIN, ALIGNED, 4, 3>(op, a, st, between);
-    if (T <= 128) return launch_geo<Geo<32, 16, 4>, TIN, ALIGNED, 4, 3>(op, a, st, between);
-    return launch_geo<Geo<64, 16, 16>, TIN, ALIGNED, 1, 1>(op, a, st, between);
+    if (T <= 4) return launch_geo<Geo<1, 1, 1>, TIN, ALIGNED, 4, 4>(op, a, st, between, pair);
+    if (T <= 8) return launch_geo<Geo<2, 1, 1>, TIN, ALIGNED, 4, 4>(op, a, st, between, pair);
+    if (T <= 16) return launch_geo<Geo<4, 1, 1>, TIN, ALIGNED, 4, 4>(op, a, st, between, pair);
+    if (T <= 32) return launch_geo<Geo<8, 4, 1>, TIN, ALIGNED, 4, 4>(op, a, st, between, pair);
+    if (T <= 64) return launch_geo<Geo<16, 4, 4>, TIN, ALIGNED, 4, 3>(op, a, st, between, pair);
+    if (T <= 128) return launch_geo<Geo<32, 16, 4>, TIN, ALIGNED, 4, 3>(op, a, st, between, pair);
+    return launch_geo<Geo<64, 16, 16>, TIN, ALIGNED, 1, 1>(op, a, st, between, pair);
 }
 
 // op: 0 = logZ only, 1 = marginals (+ logZ).  Workspace pointers already carved by the caller.
 hipError_t launch_sequential_sum(int op, int dtype, const void* phi, const int32_t* lengths, int B, int N, int T,
                                  float* ua, float* ub, double* Oa, double* Ob, float* logZ, float* mu,
-                                 hipStream_t st, hipEvent_t between) {
-    ChainArgs a{phi, lengths, B, N, T, ua, ub, Oa, Ob, logZ, mu};
+                                 hipStream_t st, hipEvent_t between, bool exact_only, unsigned long long* mail,
+                                 int* failed) {
+    ChainArgs a{phi, lengths, B, N, T, ua, ub, Oa, Ob, logZ, mu, exact_only ? 1 : 0, nullptr};
+    // Pairs pay off when one workgroup per chain would leave at least half of the chip idle.
+    static const int cus = [] {
+        int dev = 0, n = 0;
+        if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) n = 0;
+        return n;
+    }();
+    const bool use_pairs = op == 1 && !exact_only && mail && failed && pair_supported(T) && 4 * B <= cus;
+    const PairPlan pair{use_pairs ? mail : nullptr, failed, dtype};
     const bool aligned = (T % 4) == 0;
     if (dtype == 0)
-        return aligned ? launch_T<float, true>(op, a, st, between) : launch_T<float, false>(op, a, st, between);
-    return aligned ? launch_T<uint16_t, true>(op, a, st, between) : launch_T<uint16_t, false>(op, a, st, between);
+        return aligned ? launch_T<float, true>(op, a, st, between, pair) : launch_T<float, false>(op, a, st, between, pair);
+    return aligned ? launch_T<uint16_t, true>(op, a, st, between, pair)
+                   : launch_T<uint16_t, false>(op, a, st, between, pair);
 }
 
 }  // namespace lccrf

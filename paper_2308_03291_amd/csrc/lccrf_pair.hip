@@ -1,0 +1,416 @@
+// Second pass of the marginals for large tag sets and few sequences: TWO workgroups per chain.
+//
+// With B sequences there are only 2B chains (a forward and a backward one per sequence, see
+// lccrf_chain.hip).  When 2B is well below the number of compute units, one workgroup per
+// chain leaves most of the chip idle and the pass is held back by what a single CU can stream
+// (about 50 GB/s) and issue.  Here every chain is served by a PAIR of workgroups on different
+// CUs that split each T x T matrix in two:
+//
+//   forward chain  (alpha_i(t) = sum over s): partner p owns the columns [p T/2, (p+1) T/2),
+//   backward chain (beta_{i-1}(s) = sum over t): partner p owns the rows  [p T/2, (p+1) T/2),
+//
+// so each partner produces half of the next vector from half of the matrix and needs the
+// other half from its partner once per step.  The halves travel through a small mailbox in
+// device memory: every float is packed with the step number into one 8-byte word, written
+// with a single store and polled by the receiver, so no separate flag or fence is needed
+// (about 0.8 us per exchange when both workgroups sit on the same XCD; the block index of the
+// partner differs by 8, which is how consecutive workgroups are dealt to the 8 XCDs).
+//
+// Steps are speculative only (uniform shift, see lccrf_chain.hip): a pair whose sums leave the
+// accepted range, whose sequence has no finite path, or whose partner does not answer within
+// a bounded number of polls marks the sequence as failed and stops; the one-workgroup exact
+// kernel then recomputes the failed sequences.  Correctness therefore never depends on both
+// partners being resident at the same time, only the speed does.
+#include "lccrf_device.h"
+#include "lccrf_launch.h"
+
+namespace lccrf {
+
+constexpr int kPairW = 512;        // threads per workgroup (8 waves)
+constexpr int kPairWaves = 8;
+constexpr int kPairPF = 3;         // tiles in the register ring
+constexpr int kPollLimit = 1 << 18;
+constexpr int kPairMailWords = 136;  // words per mailbox slot: up to 128 values + 3 scalars, padded
+
+__device__ __forceinline__ unsigned long long pack_word(float v, unsigned tag) {
+    return ((unsigned long long)tag << 32) | (unsigned long long)__float_as_uint(v);
+}
+
+struct PairArgs {
+    const void* phi;
+    const int32_t* lengths;
+    int B, N;
+    const float* ua;   // stored by the first pass
+    const float* ub;
+    const double* Oa;
+    const double* Ob;
+    float* logZ;
+    float* mu;
+    unsigned long long* mail;  // [2B chains][2 partners][2 slots][kPairMailWords]
+    int* failed;               // [B]
+};
+
+template <int T>
+struct PairSmem {
+    static constexpr int H = T / 2;
+    alignas(16) float vec[2][T];              // un-normalised current / next vector
+    alignas(16) float psum[kPairWaves][H];    // forward: per-wave partial column sums
+    alignas(16) float wtot[kPairWaves];       // per-wave sums of the marginals written this step
+    float red[2][4];   // [0]: partner's {half maximum, marginal sum}; [1]: this workgroup's
+    int stop;          // set when this pair must give up
+};
+
+// Exchange one step's results with the partner.  Called by all threads; wave 0 sends (its lane
+// t holds own[t], the value of the t-th entry of this partner's half), wave 1 receives.
+// extra0/extra1: two scalars that travel along (wave maximum, marginal sum).
+template <int T>
+__device__ __forceinline__ void exchange(PairSmem<T>& sm, unsigned long long* mine, unsigned long long* theirs,
+                                         const int* failed_flag, unsigned tag, int tid, int nbuf, int p,
+                                         float extra0, float extra1, bool bad) {
+    constexpr int H = T / 2;
+    const int lane = tid & 63, wave = tid >> 6;
+    unsigned long long* out = mine + (tag & 1) * kPairMailWords;
+    const unsigned long long* in = theirs + (tag & 1) * kPairMailWords;
+    if (wave == 0) {
+#pragma unroll
+        for (int q = 0; q < H / 64; ++q)
+            __hip_atomic_store(&out[lane + 64 * q], pack_word(sm.vec[nbuf][p * H + lane + 64 * q], tag),
+                               __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (lane < 3) {
+            const float x = lane == 0 ? extra0 : (lane == 1 ? extra1 : (bad ? 1.f : 0.f));
+            __hip_atomic_store(&out[H + lane], pack_word(x, tag), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+    } else if (wave == 1) {
+        // every lane polls its own words until they carry this step's tag
+        constexpr int NW = H / 64 + 1;  // value words per lane, plus one of the three scalars
+        unsigned long long w[NW];
+        bool ok = false;
+        int spins = 0;
+        while (true) {
+            ok = true;
+#pragma unroll
+            for (int q = 0; q < NW; ++q) {
+                const int idx = (q < H / 64) ? lane + 64 * q : H + (lane < 3 ? lane : 0);
+                w[q] = __hip_atomic_load(&in[idx], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                ok = ok && (unsigned)(w[q] >> 32) == tag;
+            }
+            if (__all(ok)) break;
+            if (++spins > kPollLimit ||
+                __hip_atomic_load(failed_flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0) {
+                ok = false;
+                break;
+            }
+            __builtin_amdgcn_s_sleep(2);
+        }
+        if (!__all(ok)) {
+            if (lane == 0) sm.stop = 1;
+        } else {
+#pragma unroll
+            for (int q = 0; q < H / 64; ++q) sm.vec[nbuf][(1 - p) * H + lane + 64 * q] = __uint_as_float((unsigned)w[q]);
+            const float x = __uint_as_float((unsigned)w[NW - 1]);
+            if (lane == 0) sm.red[0][0] = x;                       // partner's wave maximum
+            if (lane == 1) sm.red[0][1] = x;                       // partner's marginal sum
+            if (lane == 2 && x != 0.f) sm.stop = 1;                // partner rejected the step
+        }
+    }
+}
+
+template <int T, typename TIN>
+__global__ __launch_bounds__(kPairW) void pair_marginal_kernel(PairArgs a) {
+    constexpr int H = T / 2;
+    constexpr int ITEMS = 4;
+    static_assert(T % 128 == 0 || T == 64, "tag-set sizes this kernel is built for");
+    __shared__ PairSmem<T> sm;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    // block index -> (chain, partner): partners are 8 blocks apart so that they share an XCD
+    const int grp = blockIdx.x >> 4, low = blockIdx.x & 15;
+    const int p = low >> 3;
+    const int chain = grp * 8 + (low & 7);
+    if (chain >= 2 * a.B) return;
+    const int b = chain >> 1, dir = chain & 1;
+    const int N = a.N;
+    const int L = clamp_length(a.lengths, b, N);
+    constexpr size_t TT = (size_t)T * T;
+    const size_t vb = (size_t)b * N;
+    float* mub = a.mu + (size_t)b * N * TT;
+    int* failed = a.failed + b;
+
+    if (dir == 0) {  // positions past the end carry no edge; the two partners split the zero fill
+        float4* z = reinterpret_cast<float4*>(mub);
+        const size_t z0 = (size_t)L * TT / 4, z1 = (size_t)N * TT / 4;
+        for (size_t k = z0 + (size_t)p * kPairW + tid; k < z1; k += 2 * kPairW) z[k] = make_float4(0.f, 0.f, 0.f, 0.f);
+    }
+    if (L < 2) {  // degenerate chains go to the exact kernel
+        if (tid == 0) *failed = 1;
+        return;
+    }
+    const int h = L / 2;
+    const TIN* phib = static_cast<const TIN*>(a.phi) + (size_t)b * N * TT;
+    unsigned long long* mine = a.mail + ((size_t)chain * 2 + p) * 2 * kPairMailWords;
+    unsigned long long* theirs = a.mail + ((size_t)chain * 2 + (1 - p)) * 2 * kPairMailWords;
+
+    // log2 Z at the meeting position, identical in all four workgroups of the sequence
+    if (tid == 0) sm.stop = 0;
+    float z = LCCRF_NEG_INF;
+    if (tid < T) z = a.ua[(vb + h) * T + tid] + a.ub[(vb + h) * T + tid];
+    if (wave < (T + 63) / 64) {
+        const float wm = xor_max<1, 64>(z);
+        if (lane == 0) sm.red[0][wave] = wm;
+    }
+    __syncthreads();
+    float M = LCCRF_NEG_INF;
+#pragma unroll
+    for (int w = 0; w < (T + 63) / 64; ++w) M = fmaxf(M, sm.red[0][w]);
+    if (wave < (T + 63) / 64) {
+        const float ws = xor_sum<1, 64>(ex2(z - finite_or_zero(M)));
+        if (lane == 0) sm.red[1][wave] = ws;
+    }
+    __syncthreads();
+    float Sz = 0.f;
+#pragma unroll
+    for (int w = 0; w < (T + 63) / 64; ++w) Sz += sm.red[1][w];
+    const double lz2 = (double)(M + lg2(Sz)) + a.Oa[vb + h] + a.Ob[vb + h];
+    if (!(lz2 > -1.0e300)) {  // no finite path: the exact kernel writes the zeros
+        if (tid == 0) *failed = 1;
+        return;
+    }
+    if (dir == 0 && p == 0 && tid == 0 && a.logZ) a.logZ[b] = (float)(lz2 * kLn2);
+    __syncthreads();
+
+    float ring[kPairPF][ITEMS][4];
+    float aux[kPairPF][4];
+    double off[kPairPF];
+    int buf = 0;
+    unsigned step = 0;
+    float kappa = 0.f;
+
+    if (dir == 0) {
+        // ---------------- forward chain, columns [p H, p H + H) ----------------
+        constexpr int LPR = H / 4;          // lanes per row of the half matrix
+        constexpr int RPP = kPairW / LPR;   // rows per pass
+        static_assert(RPP * ITEMS == T, "forward geometry");
+        const int c4 = p * H + 4 * (tid % LPR), r0 = tid / LPR;
+        double O = a.Oa[vb + h];
+        if (tid < T) sm.vec[0][tid] = a.ua[(vb + h) * T + tid];  // normalised: maximum 0
+        if (tid < 8) (&sm.red[0][0])[tid] = 0.f;
+        __syncthreads();
+        auto load = [&](int i, int slot) {
+#pragma unroll
+            for (int k = 0; k < ITEMS; ++k)
+                Elem<TIN>::get4(phib + (size_t)i * TT + (size_t)(r0 + k * RPP) * T + c4, ring[slot][k]);
+            const float4 q = *reinterpret_cast<const float4*>(a.ub + (vb + i) * T + c4);
+            aux[slot][0] = q.x; aux[slot][1] = q.y; aux[slot][2] = q.z; aux[slot][3] = q.w;
+            off[slot] = a.Ob[vb + i];
+        };
+        const int first = h + 1, n = L - 1 - h;
+#pragma unroll
+        for (int s = 0; s < kPairPF; ++s) load(first + (s < n ? s : (n > 0 ? n - 1 : -1)), s);  // n = 0: position h, unused
+        int done = 0;
+        bool running = n > 0;
+        while (running) {
+#pragma unroll
+            for (int slot = 0; slot < kPairPF; ++slot) {
+                const int i = first + done;
+                ++step;
+                // normaliser = maximum over partner 0's half; marginal sum of the previous step
+                const float d = finite_or_zero(p == 0 ? sm.red[1][0] : sm.red[0][0]);
+                const float tprev = (p == 0) ? sm.red[1][1] + sm.red[0][1] : sm.red[0][1] + sm.red[1][1];
+                kappa += (tprev > 0.5f && tprev < 2.0f) ? -lg2(tprev) : 0.f;
+                O += (double)d;
+                const float K = (float)(O + off[slot] - lz2) + kappa;
+                float uac[ITEMS], gm[4], ls[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int k = 0; k < ITEMS; ++k) uac[k] = sm.vec[buf][r0 + k * RPP] - d - d;  // ua - c, c = d
+#pragma unroll
+                for (int j = 0; j < 4; ++j) gm[j] = ex2(d + aux[slot][j] + K);
+                float* mrow = mub + (size_t)i * TT + c4;
+#pragma unroll
+                for (int k = 0; k < ITEMS; ++k) {
+                    float e[4];
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        e[j] = ex2(__builtin_fmaf(ring[slot][k][j], kLog2e, uac[k]));
+                        ls[j] += e[j];
+                    }
+                    *reinterpret_cast<float4*>(mrow + (size_t)(r0 + k * RPP) * T) =
+                        make_float4(e[0] * gm[0], e[1] * gm[1], e[2] * gm[2], e[3] * gm[3]);
+                }
+                {   // refill this slot with the tile kPairPF positions ahead (clamped: always issued)
+                    const int ahead = done + kPairPF;
+                    load(first + (ahead < n ? ahead : n - 1), slot);
+                }
+                float tl = (ls[0] * gm[0] + ls[1] * gm[1]) + (ls[2] * gm[2] + ls[3] * gm[3]);
+                tl = xor_sum<1, 64>(tl);
+                if (lane == 0) sm.wtot[wave] = tl;
+#pragma unroll
+                for (int j = 0; j < 4; ++j) ls[j] = xor_sum<LPR, 64>(ls[j]);
+                if (lane < LPR) *reinterpret_cast<float4*>(&sm.psum[wave][c4 - p * H]) = make_float4(ls[0], ls[1], ls[2], ls[3]);
+                __syncthreads();
+                float rm = LCCRF_NEG_INF, tp = 0.f;
+                bool bad = false;
+                if (wave == 0) {
+#pragma unroll
+                    for (int q = 0; q < H / 64; ++q) {
+                        float S = 0.f;
+#pragma unroll
+                        for (int w = 0; w < kPairWaves; ++w) S += sm.psum[w][lane + 64 * q];
+                        const float r = d + lg2(S);
+                        bad = bad || !(S >= 0x1p-60f && S <= 0x1p60f);
+                        sm.vec[buf ^ 1][p * H + lane + 64 * q] = r;
+                        rm = fmaxf(rm, r);
+                    }
+                    rm = xor_max<1, 64>(rm);
+                    bad = !__all(!bad);
+                    tp = lane < kPairWaves ? sm.wtot[lane] : 0.f;
+                    tp = xor_sum<1, 8>(tp);
+                    tp = __shfl(tp, 0, 64);
+                    if (lane == 0) { sm.red[1][0] = rm; sm.red[1][1] = tp; if (bad) sm.stop = 1; }
+                }
+                exchange<T>(sm, mine, theirs, failed, step, tid, buf ^ 1, p, rm, tp, bad);
+                __syncthreads();
+                const bool stop = sm.stop != 0;
+                buf ^= 1;
+                if (stop) {
+                    if (tid == 0) __hip_atomic_store(failed, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    return;
+                }
+                if (++done >= n) { running = false; break; }
+            }
+        }
+    } else {
+        // ---------------- backward chain, rows [p H, p H + H) ----------------
+        constexpr int LPR = T / 4;
+        constexpr int RPP = kPairW / LPR;
+        static_assert(RPP * ITEMS == H, "backward geometry");
+        const int c4 = 4 * (tid % LPR), r0 = p * H + tid / LPR;
+        double O = a.Ob[vb + h];
+        if (tid < T) sm.vec[0][tid] = a.ub[(vb + h) * T + tid];
+        if (tid < 8) (&sm.red[0][0])[tid] = 0.f;
+        __syncthreads();
+        auto load = [&](int i, int slot) {
+#pragma unroll
+            for (int k = 0; k < ITEMS; ++k) {
+                Elem<TIN>::get4(phib + (size_t)i * TT + (size_t)(r0 + k * RPP) * T + c4, ring[slot][k]);
+                aux[slot][k] = a.ua[(vb + i - 1) * T + r0 + k * RPP];
+            }
+            off[slot] = a.Oa[vb + i - 1];
+        };
+        const int first = h, n = h;  // positions h, h-1, ..., 1
+#pragma unroll
+        for (int s = 0; s < kPairPF; ++s) load(first - (s < n ? s : n - 1), s);
+        int done = 0;
+        bool running = true;
+        while (running) {
+#pragma unroll
+            for (int slot = 0; slot < kPairPF; ++slot) {
+                const int i = first - done;
+                ++step;
+                // normaliser = maximum over partner 0's half; marginal sum of the previous step
+                const float d = finite_or_zero(p == 0 ? sm.red[1][0] : sm.red[0][0]);
+                const float tprev = (p == 0) ? sm.red[1][1] + sm.red[0][1] : sm.red[0][1] + sm.red[1][1];
+                kappa += (tprev > 0.5f && tprev < 2.0f) ? -lg2(tprev) : 0.f;
+                O += (double)d;
+                const float K = (float)(off[slot] + O - lz2) + kappa;
+                const float4 q = *reinterpret_cast<const float4*>(&sm.vec[buf][c4]);
+                const float ubc[4] = {q.x - d - d, q.y - d - d, q.z - d - d, q.w - d - d};  // ub - c, c = d
+                float S[ITEMS];
+                float tl = 0.f;
+                float* mrow = mub + (size_t)i * TT + c4;
+#pragma unroll
+                for (int k = 0; k < ITEMS; ++k) {
+                    float e[4];
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) e[j] = ex2(__builtin_fmaf(ring[slot][k][j], kLog2e, ubc[j]));
+                    S[k] = (e[0] + e[1]) + (e[2] + e[3]);
+                    const float f = ex2(d + aux[slot][k] + K);
+                    *reinterpret_cast<float4*>(mrow + (size_t)(r0 + k * RPP) * T) =
+                        make_float4(e[0] * f, e[1] * f, e[2] * f, e[3] * f);
+                    tl += S[k] * f;
+                }
+                {
+                    const int ahead = done + kPairPF;
+                    load(first - (ahead < n ? ahead : n - 1), slot);
+                }
+                bool bad = false;
+#pragma unroll
+                for (int k = 0; k < ITEMS; ++k) {
+                    const float Sk = xor_sum<1, LPR < 64 ? LPR : 64>(S[k]);
+                    bad = bad || !(Sk >= 0x1p-60f && Sk <= 0x1p60f);
+                    if (c4 == 0) sm.vec[buf ^ 1][r0 + k * RPP] = d + lg2(Sk);
+                }
+                tl = xor_sum<1, 64>(tl);
+                if (lane == 0) sm.wtot[wave] = tl;
+                if (!__all(!bad) && lane == 0) sm.stop = 1;
+                __syncthreads();
+                float rm = LCCRF_NEG_INF, tp = 0.f;
+                if (wave == 0) {
+#pragma unroll
+                    for (int qq = 0; qq < H / 64; ++qq) rm = fmaxf(rm, sm.vec[buf ^ 1][p * H + lane + 64 * qq]);
+                    rm = xor_max<1, 64>(rm);
+                    tp = lane < kPairWaves ? sm.wtot[lane] : 0.f;
+                    tp = xor_sum<1, 8>(tp);
+                    tp = __shfl(tp, 0, 64);
+                    if (lane == 0) { sm.red[1][0] = rm; sm.red[1][1] = tp; }
+                }
+                exchange<T>(sm, mine, theirs, failed, step, tid, buf ^ 1, p, rm, tp, sm.stop != 0);
+                __syncthreads();
+                const bool stop = sm.stop != 0;
+                buf ^= 1;
+                if (stop) {
+                    if (tid == 0) __hip_atomic_store(failed, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    return;
+                }
+                if (++done >= n) { running = false; break; }
+            }
+        }
+        // position 0: p(y_0 = t) = softmax_t(alpha_0(t) + beta_0(t)) in row 0, zeros elsewhere
+        for (int k = T + p * kPairW + tid; k < (int)TT; k += 2 * kPairW) mub[k] = 0.f;
+        if (p == 0 && wave == 0) {
+            float m = LCCRF_NEG_INF;
+            for (int t = lane; t < T; t += 64) m = fmaxf(m, a.ua[vb * T + t] + sm.vec[buf][t]);
+            m = xor_max<1, 64>(m);
+            float S = 0.f;
+            for (int t = lane; t < T; t += 64) S += ex2(a.ua[vb * T + t] + sm.vec[buf][t] - finite_or_zero(m));
+            S = xor_sum<1, 64>(S);
+            const float cinv = S > 0.f ? 1.0f / S : 0.f;
+            for (int t = lane; t < T; t += 64) mub[t] = cinv * ex2(a.ua[vb * T + t] + sm.vec[buf][t] - finite_or_zero(m));
+        }
+    }
+}
+
+// Clears the mailboxes and the per-sequence failure flags.
+__global__ void pair_reset_kernel(unsigned long long* mail, size_t words, int* failed, int B) {
+    const size_t k = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (k < words) mail[k] = 0ull;
+    if (k < (size_t)B) failed[k] = 0;
+}
+
+size_t pair_mail_words(int B) { return (size_t)2 * B * 2 * 2 * kPairMailWords; }
+
+bool pair_supported(int T) { return T == 128; }
+
+hipError_t launch_pair_marginals(int dtype, const void* phi, const int32_t* lengths, int B, int N, int T,
+                                 const float* ua, const float* ub, const double* Oa, const double* Ob,
+                                 float* logZ, float* mu, unsigned long long* mail, int* failed, hipStream_t st) {
+    PairArgs a{phi, lengths, B, N, ua, ub, Oa, Ob, logZ, mu, mail, failed};
+    const int chains = 2 * B;
+    const int grid = ((chains + 7) / 8) * 16;
+    if (T == 128) {
+        if (dtype == 0)
+            hipLaunchKernelGGL((pair_marginal_kernel<128, float>), dim3(grid), dim3(kPairW), 0, st, a);
+        else
+            hipLaunchKernelGGL((pair_marginal_kernel<128, uint16_t>), dim3(grid), dim3(kPairW), 0, st, a);
+    } else {
+        return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
+}
+
+hipError_t launch_pair_reset(unsigned long long* mail, int B, int* failed, hipStream_t st) {
+    const size_t words = pair_mail_words(B);
+    const size_t n = words > (size_t)B ? words : (size_t)B;
+    hipLaunchKernelGGL(pair_reset_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, mail, words, failed, B);
+    return hipGetLastError();
+}
+
+}  // namespace lccrf

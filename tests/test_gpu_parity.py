@@ -244,6 +244,76 @@ def test_dirty_workspace_and_side_stream(crf, oracle_mod):
 
 
 # ---------------------------------------------------------------------------------------
+# the two step flavours of the sequential schedule
+
+@pytest.mark.parametrize("T,N", [(5, 8), (16, 40), (32, 64), (48, 33), (100, 9), (128, 12), (255, 4)])
+def test_exact_schedule(crf, oracle_mod, T, N):
+    """Every position through the exact step (the one that otherwise only replays rejected
+    speculative steps)."""
+    phi, lens = workloads.random_case(4000 + T, 4, N, T, scale=2.0, ragged=True, min_len=1)
+    check_case(crf, oracle_mod, phi, lens, algo=crf.ALGO_SEQUENTIAL_EXACT, what=f"exact T={T} N={N}",
+               queries=("logz", "mu"))
+
+
+@pytest.mark.parametrize("T,N", [(16, 64), (32, 40), (48, 21), (128, 10)])
+def test_scale_jumps_force_replays(crf, oracle_mod, T, N):
+    """Potentials whose scale jumps by hundreds of nats between neighbouring positions: the
+    speculative step (shift = previous normaliser) must be rejected and replayed exactly, also
+    in the middle of a chain and in both directions."""
+    phi, lens = workloads.random_case(4100 + T, 3, N, T, scale=1.0, ragged=True, min_len=N // 2)
+    g = torch.Generator().manual_seed(99 + T)
+    jump = (torch.randint(0, 3, (3, N, 1, 1), generator=g).to(torch.float32) - 1.0) * 300.0
+    jump[:, ::5] = 0.0
+    phi = (phi + jump).contiguous()
+    check_case(crf, oracle_mod, phi, lens, what=f"jumps T={T} N={N}", queries=("logz", "mu"))
+
+
+@pytest.mark.parametrize("N,lens", [(2, [2, 1, 0]), (3, [3, 2, 3]), (9, [9, 4, 7]), (40, [40, 33, 5]), (65, [65, 64, 2])])
+def test_paired_second_pass(crf, oracle_mod, N, lens):
+    """T = 128 with few sequences: the default schedule serves every chain with two workgroups
+    that exchange half vectors each step; it must agree with the oracle and, closely, with the
+    one-workgroup-per-chain schedule."""
+    T = 128
+    phi, _ = workloads.random_case(4200 + N, len(lens), N, T, scale=1.3)
+    lens_t = torch.tensor(lens, dtype=torch.int32)
+    check_case(crf, oracle_mod, phi, lens_t, what=f"paired N={N}", queries=("mu",))
+    dphi, dl = phi.cuda(), lens_t.cuda()
+    lz_a, mu_a = crf.lccrf_marginals(dphi, dl)
+    lz_b, mu_b = crf.lccrf_marginals(dphi, dl, algo=crf.ALGO_SEQUENTIAL)
+    assert torch.allclose(lz_a, lz_b, rtol=1e-6, atol=1e-6)
+    assert float((mu_a - mu_b).abs().max()) < 2e-6
+
+
+def test_paired_second_pass_hands_failures_to_the_exact_kernel(crf, oracle_mod):
+    """Sequences the paired speculative pass must give up on (forbidden edges, no finite path,
+    scale jumps) are recomputed exactly; the others in the same batch are not disturbed."""
+    T, N = 128, 12
+    phi, _ = workloads.random_case(4300, 5, N, T)
+    ninf = float("-inf")
+    phi[1, 5, :, 7] = ninf                       # a forbidden tag
+    phi[2, 8, :, :] = ninf                       # no finite path at all
+    phi[3, 3] += 400.0                           # scale jump in the forward half
+    phi[3, 9] -= 400.0                           # and in the backward half
+    lens = torch.tensor([12, 12, 12, 12, 11], dtype=torch.int32)
+    check_case(crf, oracle_mod, phi, lens, poison=False, what="paired failures", queries=("logz", "mu"))
+
+
+def test_paired_second_pass_bf16(crf, oracle_mod):
+    phi, _ = workloads.random_case(4400, 2, 30, 128, scale=3.0, dtype="bf16")
+    check_case(crf, oracle_mod, phi, None, poison=False, what="paired bf16", queries=("mu",))
+
+
+def test_speculative_and_exact_agree_closely(crf):
+    w = workloads.WORKLOADS["cfg2"]
+    phi = workloads.phi_batch(w).cuda()
+    lens = workloads.lengths(w).cuda()
+    lz_a, mu_a = crf.lccrf_marginals(phi, lens)
+    lz_b, mu_b = crf.lccrf_marginals(phi, lens, algo=crf.ALGO_SEQUENTIAL_EXACT)
+    assert torch.allclose(lz_a, lz_b, rtol=1e-6, atol=0)
+    assert float((mu_a - mu_b).abs().max()) < 2e-6
+
+
+# ---------------------------------------------------------------------------------------
 # the named workloads
 
 @pytest.mark.parametrize("key", ["cfg1", "cfg2", "cfg3"])
