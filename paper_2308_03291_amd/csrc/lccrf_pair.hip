@@ -26,14 +26,17 @@
 
 namespace lccrf {
 
-constexpr int kPairW = 512;        // threads per workgroup (8 waves)
+constexpr int kPairW = 512;        // threads that load and compute (8 waves)
 constexpr int kPairWaves = 8;
-constexpr int kPairPF = 3;         // tiles in the register ring
+constexpr int kPairThreads = kPairW + 64;  // plus one wave that only receives the partner's half
+constexpr int kPairPF = 4;         // tiles in the register ring
 constexpr int kPollLimit = 1 << 18;
-constexpr int kPairMailWords = 136;  // words per mailbox slot: up to 128 values + 3 scalars, padded
+constexpr int kPairMailWords = 128;  // words per mailbox slot (one per entry of a half vector, T <= 256)
 
-__device__ __forceinline__ unsigned long long pack_word(float v, unsigned tag) {
-    return ((unsigned long long)tag << 32) | (unsigned long long)__float_as_uint(v);
+// One mailbox word: [tag:16][extra:16][value:32], written and read as one 8-byte access, so a
+// word whose tag matches carries this step's value; no flag, no fence.
+__device__ __forceinline__ unsigned long long pack_word(float v, unsigned tag, unsigned extra) {
+    return ((unsigned long long)(((tag & 0xffffu) << 16) | (extra & 0xffffu)) << 32) | (unsigned long long)__float_as_uint(v);
 }
 
 struct PairArgs {
@@ -56,72 +59,87 @@ struct PairSmem {
     alignas(16) float vec[2][T];              // un-normalised current / next vector
     alignas(16) float psum[kPairWaves][H];    // forward: per-wave partial column sums
     alignas(16) float wtot[kPairWaves];       // per-wave sums of the marginals written this step
-    float red[2][4];   // [0]: partner's {half maximum, marginal sum}; [1]: this workgroup's
+    float red[2][4];   // scratch of the mid-point log-sum-exp
+    float dmax[2];     // normaliser of vec[buf]: maximum over partner 0's half
+    float tot_own[2];  // marginal sum of the step that produced vec[buf]: this workgroup's part
+    float tot_oth[2];  // ... and the partner's part
     int stop;          // set when this pair must give up
 };
 
-// Exchange one step's results with the partner.  Called by all threads; wave 0 sends (its lane
-// t holds own[t], the value of the t-th entry of this partner's half), wave 1 receives.
-// extra0/extra1: two scalars that travel along (wave maximum, marginal sum).
+// Sender side, executed by wave 0 right after it has its part of the next vector in `r`
+// (lane t holds entry t + 64 q of this partner's half): one store per entry.  The marginal sum
+// of the step rides in the extra bits of lanes 0 and 1, the "step rejected" vote in lane 2's.
 template <int T>
-__device__ __forceinline__ void exchange(PairSmem<T>& sm, unsigned long long* mine, unsigned long long* theirs,
-                                         const int* failed_flag, unsigned tag, int tid, int nbuf, int p,
-                                         float extra0, float extra1, bool bad) {
-    constexpr int H = T / 2;
-    const int lane = tid & 63, wave = tid >> 6;
+__device__ __forceinline__ void send_half(unsigned long long* mine, unsigned tag, int lane,
+                                          const float (&r)[T / 128 ? T / 128 : 1], float tot, bool bad) {
     unsigned long long* out = mine + (tag & 1) * kPairMailWords;
+    const unsigned tb = __float_as_uint(tot);
+    const unsigned extra = lane == 0 ? (tb >> 16) : (lane == 1 ? (tb & 0xffffu) : (lane == 2 ? (bad ? 1u : 0u) : 0u));
+#pragma unroll
+    for (int q = 0; q < (T / 128 ? T / 128 : 1); ++q)
+        __hip_atomic_store(&out[lane + 64 * q], pack_word(r[q], tag, q == 0 ? extra : 0u), __ATOMIC_RELAXED,
+                           __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// Receiver side, executed by the extra wave only: polls the partner's words of this step,
+// puts the partner's half into vec[nbuf] and its scalars into shared memory.  Sets sm.stop if
+// the partner rejected the step, if the sequence has been flagged as failed, or if nothing
+// arrives within kPollLimit polls.
+template <int T>
+__device__ __forceinline__ void receive_half(PairSmem<T>& sm, const unsigned long long* theirs, const int* failed_flag,
+                                             unsigned tag, int lane, int nbuf, int p) {
+    constexpr int H = T / 2;
+    constexpr int NQ = H / 64;
     const unsigned long long* in = theirs + (tag & 1) * kPairMailWords;
-    if (wave == 0) {
+    unsigned long long w[NQ];
+    bool ok = false;
+    int spins = 0;
+    while (true) {
+        ok = true;
 #pragma unroll
-        for (int q = 0; q < H / 64; ++q)
-            __hip_atomic_store(&out[lane + 64 * q], pack_word(sm.vec[nbuf][p * H + lane + 64 * q], tag),
-                               __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        if (lane < 3) {
-            const float x = lane == 0 ? extra0 : (lane == 1 ? extra1 : (bad ? 1.f : 0.f));
-            __hip_atomic_store(&out[H + lane], pack_word(x, tag), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        for (int q = 0; q < NQ; ++q) {
+            w[q] = __hip_atomic_load(&in[lane + 64 * q], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            ok = ok && (unsigned)(w[q] >> 48) == (tag & 0xffffu);
         }
-    } else if (wave == 1) {
-        // every lane polls its own words until they carry this step's tag
-        constexpr int NW = H / 64 + 1;  // value words per lane, plus one of the three scalars
-        unsigned long long w[NW];
-        bool ok = false;
-        int spins = 0;
-        while (true) {
-            ok = true;
+        if (__all(ok)) break;
+        if (++spins > kPollLimit || __hip_atomic_load(failed_flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0) {
+            ok = false;
+            break;
+        }
+    }
+    if (!__all(ok)) {
+        if (lane == 0) sm.stop = 1;
+        return;
+    }
+    float m = LCCRF_NEG_INF;
 #pragma unroll
-            for (int q = 0; q < NW; ++q) {
-                const int idx = (q < H / 64) ? lane + 64 * q : H + (lane < 3 ? lane : 0);
-                w[q] = __hip_atomic_load(&in[idx], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                ok = ok && (unsigned)(w[q] >> 32) == tag;
-            }
-            if (__all(ok)) break;
-            if (++spins > kPollLimit ||
-                __hip_atomic_load(failed_flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0) {
-                ok = false;
-                break;
-            }
-            __builtin_amdgcn_s_sleep(2);
-        }
-        if (!__all(ok)) {
-            if (lane == 0) sm.stop = 1;
-        } else {
-#pragma unroll
-            for (int q = 0; q < H / 64; ++q) sm.vec[nbuf][(1 - p) * H + lane + 64 * q] = __uint_as_float((unsigned)w[q]);
-            const float x = __uint_as_float((unsigned)w[NW - 1]);
-            if (lane == 0) sm.red[0][0] = x;                       // partner's wave maximum
-            if (lane == 1) sm.red[0][1] = x;                       // partner's marginal sum
-            if (lane == 2 && x != 0.f) sm.stop = 1;                // partner rejected the step
-        }
+    for (int q = 0; q < NQ; ++q) {
+        const float v = __uint_as_float((unsigned)w[q]);
+        sm.vec[nbuf][(1 - p) * H + lane + 64 * q] = v;
+        m = fmaxf(m, v);
+    }
+    const unsigned extra = (unsigned)(w[0] >> 32) & 0xffffu;
+    const unsigned hi = __builtin_amdgcn_readlane(extra, 0), lo = __builtin_amdgcn_readlane(extra, 1);
+    const unsigned badbit = __builtin_amdgcn_readlane(extra, 2);
+    if (p == 1) {  // the normaliser is the maximum over partner 0's half, which is what arrived here
+        m = xor_max<1, 64>(m);
+        if (lane == 0) sm.dmax[nbuf] = finite_or_zero(m);
+    }
+    if (lane == 0) {
+        sm.tot_oth[nbuf] = __uint_as_float((hi << 16) | lo);
+        if (badbit) sm.stop = 1;
     }
 }
 
 template <int T, typename TIN>
-__global__ __launch_bounds__(kPairW) void pair_marginal_kernel(PairArgs a) {
+__global__ __launch_bounds__(kPairThreads) void pair_marginal_kernel(PairArgs a) {
     constexpr int H = T / 2;
     constexpr int ITEMS = 4;
-    static_assert(T % 128 == 0 || T == 64, "tag-set sizes this kernel is built for");
+    constexpr int NQ = H / 64;
+    static_assert(T == 128 || T == 256, "tag-set sizes this kernel is built for");
     __shared__ PairSmem<T> sm;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const bool worker = wave < kPairWaves;
     // block index -> (chain, partner): partners are 8 blocks apart so that they share an XCD
     const int grp = blockIdx.x >> 4, low = blockIdx.x & 15;
     const int p = low >> 3;
@@ -135,7 +153,7 @@ __global__ __launch_bounds__(kPairW) void pair_marginal_kernel(PairArgs a) {
     float* mub = a.mu + (size_t)b * N * TT;
     int* failed = a.failed + b;
 
-    if (dir == 0) {  // positions past the end carry no edge; the two partners split the zero fill
+    if (dir == 0 && worker) {  // positions past the end carry no edge; the two partners split the zero fill
         float4* z = reinterpret_cast<float4*>(mub);
         const size_t z0 = (size_t)L * TT / 4, z1 = (size_t)N * TT / 4;
         for (size_t k = z0 + (size_t)p * kPairW + tid; k < z1; k += 2 * kPairW) z[k] = make_float4(0.f, 0.f, 0.f, 0.f);
@@ -147,7 +165,7 @@ __global__ __launch_bounds__(kPairW) void pair_marginal_kernel(PairArgs a) {
     const int h = L / 2;
     const TIN* phib = static_cast<const TIN*>(a.phi) + (size_t)b * N * TT;
     unsigned long long* mine = a.mail + ((size_t)chain * 2 + p) * 2 * kPairMailWords;
-    unsigned long long* theirs = a.mail + ((size_t)chain * 2 + (1 - p)) * 2 * kPairMailWords;
+    const unsigned long long* theirs = a.mail + ((size_t)chain * 2 + (1 - p)) * 2 * kPairMailWords;
 
     // log2 Z at the meeting position, identical in all four workgroups of the sequence
     if (tid == 0) sm.stop = 0;
@@ -175,13 +193,34 @@ __global__ __launch_bounds__(kPairW) void pair_marginal_kernel(PairArgs a) {
         return;
     }
     if (dir == 0 && p == 0 && tid == 0 && a.logZ) a.logZ[b] = (float)(lz2 * kLn2);
+
+    // the vector both chains start from (normalised in the first pass: maximum 0)
+    const float* start = (dir == 0 ? a.ua : a.ub) + (vb + h) * T;
+    if (tid < T) sm.vec[0][tid] = start[tid];
+    if (tid == 0) { sm.dmax[0] = 0.f; sm.tot_own[0] = 0.f; sm.tot_oth[0] = 0.f; }
     __syncthreads();
+
+    const int n = (dir == 0) ? L - 1 - h : h;  // number of positions this pair walks
+    // Every step has exactly two workgroup barriers, in the receiver wave as in the workers:
+    //   A: the workers' partial results are in shared memory;
+    //   B: both halves of the next vector (and its scalars) are in shared memory.
+    if (!worker) {
+        // ---------------- receiver wave ----------------
+        int buf = 0;
+        for (int done = 0; done < n; ++done) {
+            __syncthreads();  // A
+            receive_half<T>(sm, theirs, failed, (unsigned)(done + 1), lane, buf ^ 1, p);
+            __syncthreads();  // B
+            buf ^= 1;
+            if (sm.stop != 0) return;
+        }
+        return;
+    }
 
     float ring[kPairPF][ITEMS][4];
     float aux[kPairPF][4];
     double off[kPairPF];
     int buf = 0;
-    unsigned step = 0;
     float kappa = 0.f;
 
     if (dir == 0) {
@@ -191,9 +230,6 @@ __global__ __launch_bounds__(kPairW) void pair_marginal_kernel(PairArgs a) {
         static_assert(RPP * ITEMS == T, "forward geometry");
         const int c4 = p * H + 4 * (tid % LPR), r0 = tid / LPR;
         double O = a.Oa[vb + h];
-        if (tid < T) sm.vec[0][tid] = a.ua[(vb + h) * T + tid];  // normalised: maximum 0
-        if (tid < 8) (&sm.red[0][0])[tid] = 0.f;
-        __syncthreads();
         auto load = [&](int i, int slot) {
 #pragma unroll
             for (int k = 0; k < ITEMS; ++k)
@@ -202,7 +238,7 @@ __global__ __launch_bounds__(kPairW) void pair_marginal_kernel(PairArgs a) {
             aux[slot][0] = q.x; aux[slot][1] = q.y; aux[slot][2] = q.z; aux[slot][3] = q.w;
             off[slot] = a.Ob[vb + i];
         };
-        const int first = h + 1, n = L - 1 - h;
+        const int first = h + 1;
 #pragma unroll
         for (int s = 0; s < kPairPF; ++s) load(first + (s < n ? s : (n > 0 ? n - 1 : -1)), s);  // n = 0: position h, unused
         int done = 0;
@@ -211,16 +247,14 @@ __global__ __launch_bounds__(kPairW) void pair_marginal_kernel(PairArgs a) {
 #pragma unroll
             for (int slot = 0; slot < kPairPF; ++slot) {
                 const int i = first + done;
-                ++step;
-                // normaliser = maximum over partner 0's half; marginal sum of the previous step
-                const float d = finite_or_zero(p == 0 ? sm.red[1][0] : sm.red[0][0]);
-                const float tprev = (p == 0) ? sm.red[1][1] + sm.red[0][1] : sm.red[0][1] + sm.red[1][1];
+                const float d = sm.dmax[buf];
+                const float tprev = (p == 0) ? sm.tot_own[buf] + sm.tot_oth[buf] : sm.tot_oth[buf] + sm.tot_own[buf];
                 kappa += (tprev > 0.5f && tprev < 2.0f) ? -lg2(tprev) : 0.f;
                 O += (double)d;
                 const float K = (float)(O + off[slot] - lz2) + kappa;
                 float uac[ITEMS], gm[4], ls[4] = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-                for (int k = 0; k < ITEMS; ++k) uac[k] = sm.vec[buf][r0 + k * RPP] - d - d;  // ua - c, c = d
+                for (int k = 0; k < ITEMS; ++k) uac[k] = sm.vec[buf][r0 + k * RPP] - d - d;  // ua - c, shift c = d
 #pragma unroll
                 for (int j = 0; j < 4; ++j) gm[j] = ex2(d + aux[slot][j] + K);
                 float* mrow = mub + (size_t)i * TT + c4;
@@ -245,32 +279,36 @@ __global__ __launch_bounds__(kPairW) void pair_marginal_kernel(PairArgs a) {
 #pragma unroll
                 for (int j = 0; j < 4; ++j) ls[j] = xor_sum<LPR, 64>(ls[j]);
                 if (lane < LPR) *reinterpret_cast<float4*>(&sm.psum[wave][c4 - p * H]) = make_float4(ls[0], ls[1], ls[2], ls[3]);
-                __syncthreads();
-                float rm = LCCRF_NEG_INF, tp = 0.f;
-                bool bad = false;
+                __syncthreads();  // A
                 if (wave == 0) {
+                    float r[NQ];
+                    bool bad = false;
 #pragma unroll
-                    for (int q = 0; q < H / 64; ++q) {
+                    for (int q = 0; q < NQ; ++q) {
                         float S = 0.f;
 #pragma unroll
                         for (int w = 0; w < kPairWaves; ++w) S += sm.psum[w][lane + 64 * q];
-                        const float r = d + lg2(S);
+                        r[q] = d + lg2(S);
                         bad = bad || !(S >= 0x1p-60f && S <= 0x1p60f);
-                        sm.vec[buf ^ 1][p * H + lane + 64 * q] = r;
-                        rm = fmaxf(rm, r);
                     }
-                    rm = xor_max<1, 64>(rm);
                     bad = !__all(!bad);
-                    tp = lane < kPairWaves ? sm.wtot[lane] : 0.f;
+                    float tp = lane < kPairWaves ? sm.wtot[lane] : 0.f;
                     tp = xor_sum<1, 8>(tp);
-                    tp = __shfl(tp, 0, 64);
-                    if (lane == 0) { sm.red[1][0] = rm; sm.red[1][1] = tp; if (bad) sm.stop = 1; }
+                    tp = __builtin_amdgcn_readfirstlane(tp);
+                    send_half<T>(mine, (unsigned)(done + 1), lane, r, tp, bad);
+                    float rm = LCCRF_NEG_INF;
+#pragma unroll
+                    for (int q = 0; q < NQ; ++q) { sm.vec[buf ^ 1][p * H + lane + 64 * q] = r[q]; rm = fmaxf(rm, r[q]); }
+                    if (p == 0) rm = xor_max<1, 64>(rm);
+                    if (lane == 0) {
+                        if (p == 0) sm.dmax[buf ^ 1] = finite_or_zero(rm);
+                        sm.tot_own[buf ^ 1] = tp;
+                        if (bad) sm.stop = 1;
+                    }
                 }
-                exchange<T>(sm, mine, theirs, failed, step, tid, buf ^ 1, p, rm, tp, bad);
-                __syncthreads();
-                const bool stop = sm.stop != 0;
+                __syncthreads();  // B
                 buf ^= 1;
-                if (stop) {
+                if (sm.stop != 0) {
                     if (tid == 0) __hip_atomic_store(failed, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                     return;
                 }
@@ -281,12 +319,9 @@ __global__ __launch_bounds__(kPairW) void pair_marginal_kernel(PairArgs a) {
         // ---------------- backward chain, rows [p H, p H + H) ----------------
         constexpr int LPR = T / 4;
         constexpr int RPP = kPairW / LPR;
-        static_assert(RPP * ITEMS == H, "backward geometry");
+        static_assert(RPP * ITEMS == H && LPR <= 64, "backward geometry");
         const int c4 = 4 * (tid % LPR), r0 = p * H + tid / LPR;
         double O = a.Ob[vb + h];
-        if (tid < T) sm.vec[0][tid] = a.ub[(vb + h) * T + tid];
-        if (tid < 8) (&sm.red[0][0])[tid] = 0.f;
-        __syncthreads();
         auto load = [&](int i, int slot) {
 #pragma unroll
             for (int k = 0; k < ITEMS; ++k) {
@@ -295,7 +330,7 @@ __global__ __launch_bounds__(kPairW) void pair_marginal_kernel(PairArgs a) {
             }
             off[slot] = a.Oa[vb + i - 1];
         };
-        const int first = h, n = h;  // positions h, h-1, ..., 1
+        const int first = h;  // positions h, h-1, ..., 1
 #pragma unroll
         for (int s = 0; s < kPairPF; ++s) load(first - (s < n ? s : n - 1), s);
         int done = 0;
@@ -304,15 +339,13 @@ __global__ __launch_bounds__(kPairW) void pair_marginal_kernel(PairArgs a) {
 #pragma unroll
             for (int slot = 0; slot < kPairPF; ++slot) {
                 const int i = first - done;
-                ++step;
-                // normaliser = maximum over partner 0's half; marginal sum of the previous step
-                const float d = finite_or_zero(p == 0 ? sm.red[1][0] : sm.red[0][0]);
-                const float tprev = (p == 0) ? sm.red[1][1] + sm.red[0][1] : sm.red[0][1] + sm.red[1][1];
+                const float d = sm.dmax[buf];
+                const float tprev = (p == 0) ? sm.tot_own[buf] + sm.tot_oth[buf] : sm.tot_oth[buf] + sm.tot_own[buf];
                 kappa += (tprev > 0.5f && tprev < 2.0f) ? -lg2(tprev) : 0.f;
                 O += (double)d;
                 const float K = (float)(off[slot] + O - lz2) + kappa;
-                const float4 q = *reinterpret_cast<const float4*>(&sm.vec[buf][c4]);
-                const float ubc[4] = {q.x - d - d, q.y - d - d, q.z - d - d, q.w - d - d};  // ub - c, c = d
+                const float4 q4 = *reinterpret_cast<const float4*>(&sm.vec[buf][c4]);
+                const float ubc[4] = {q4.x - d - d, q4.y - d - d, q4.z - d - d, q4.w - d - d};  // ub - c, shift c = d
                 float S[ITEMS];
                 float tl = 0.f;
                 float* mrow = mub + (size_t)i * TT + c4;
@@ -334,29 +367,32 @@ __global__ __launch_bounds__(kPairW) void pair_marginal_kernel(PairArgs a) {
                 bool bad = false;
 #pragma unroll
                 for (int k = 0; k < ITEMS; ++k) {
-                    const float Sk = xor_sum<1, LPR < 64 ? LPR : 64>(S[k]);
+                    const float Sk = xor_sum<1, LPR>(S[k]);
                     bad = bad || !(Sk >= 0x1p-60f && Sk <= 0x1p60f);
                     if (c4 == 0) sm.vec[buf ^ 1][r0 + k * RPP] = d + lg2(Sk);
                 }
                 tl = xor_sum<1, 64>(tl);
                 if (lane == 0) sm.wtot[wave] = tl;
                 if (!__all(!bad) && lane == 0) sm.stop = 1;
-                __syncthreads();
-                float rm = LCCRF_NEG_INF, tp = 0.f;
+                __syncthreads();  // A
                 if (wave == 0) {
+                    float r[NQ];
+                    float rm = LCCRF_NEG_INF;
 #pragma unroll
-                    for (int qq = 0; qq < H / 64; ++qq) rm = fmaxf(rm, sm.vec[buf ^ 1][p * H + lane + 64 * qq]);
-                    rm = xor_max<1, 64>(rm);
-                    tp = lane < kPairWaves ? sm.wtot[lane] : 0.f;
+                    for (int q = 0; q < NQ; ++q) { r[q] = sm.vec[buf ^ 1][p * H + lane + 64 * q]; rm = fmaxf(rm, r[q]); }
+                    float tp = lane < kPairWaves ? sm.wtot[lane] : 0.f;
                     tp = xor_sum<1, 8>(tp);
-                    tp = __shfl(tp, 0, 64);
-                    if (lane == 0) { sm.red[1][0] = rm; sm.red[1][1] = tp; }
+                    tp = __builtin_amdgcn_readfirstlane(tp);
+                    send_half<T>(mine, (unsigned)(done + 1), lane, r, tp, sm.stop != 0);
+                    if (p == 0) rm = xor_max<1, 64>(rm);
+                    if (lane == 0) {
+                        if (p == 0) sm.dmax[buf ^ 1] = finite_or_zero(rm);
+                        sm.tot_own[buf ^ 1] = tp;
+                    }
                 }
-                exchange<T>(sm, mine, theirs, failed, step, tid, buf ^ 1, p, rm, tp, sm.stop != 0);
-                __syncthreads();
-                const bool stop = sm.stop != 0;
+                __syncthreads();  // B
                 buf ^= 1;
-                if (stop) {
+                if (sm.stop != 0) {
                     if (tid == 0) __hip_atomic_store(failed, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                     return;
                 }
@@ -397,9 +433,9 @@ hipError_t launch_pair_marginals(int dtype, const void* phi, const int32_t* leng
     const int grid = ((chains + 7) / 8) * 16;
     if (T == 128) {
         if (dtype == 0)
-            hipLaunchKernelGGL((pair_marginal_kernel<128, float>), dim3(grid), dim3(kPairW), 0, st, a);
+            hipLaunchKernelGGL((pair_marginal_kernel<128, float>), dim3(grid), dim3(kPairThreads), 0, st, a);
         else
-            hipLaunchKernelGGL((pair_marginal_kernel<128, uint16_t>), dim3(grid), dim3(kPairW), 0, st, a);
+            hipLaunchKernelGGL((pair_marginal_kernel<128, uint16_t>), dim3(grid), dim3(kPairThreads), 0, st, a);
     } else {
         return hipErrorInvalidValue;
     }
