@@ -9,9 +9,9 @@ the timed region starts.  The headline number is potentials per second, B*N*T*T 
 step.  Prints exactly one JSON line on stdout; everything else goes to stderr.
 
 Extra objects in the line:
-  roofline      for the dominant kernel (the pass that re-reads phi and writes the marginals),
-                timed with HIP events the library records on the launch stream between its
-                passes: algorithmic bytes = (sizeof(phi element) + 4) per potential.
+  roofline      for the dominant kernel (the second pass, which re-reads phi and writes the
+                marginals), timed with HIP events the library records on the launch stream
+                between its passes: algorithmic bytes = (sizeof(phi element) + 4) per potential.
   cpu_baseline  the CPU oracle (as it stands, OpenMP over the batch) timed on this host on a
                 bounded sample of the same workload.
   other_queries log-partition alone and Viterbi decode, timed the same way (context).
@@ -164,7 +164,11 @@ def main():
     alg_bytes = eff_pots * (esz + 4)
     achieved = alg_bytes / (pass2_avg * 1e-3) / 1e9
     call_bytes = eff_pots * (2 * esz + 4)
-    roofline = {"bound": "hbm", "kernel": "chain_marginal_kernel", "achieved": achieved, "peak": HBM_PEAK_GBPS,
+    # With few sequences and T = 128 that pass is the two-workgroups-per-chain kernel (plus two
+    # few-microsecond helpers the event interval also covers: mailbox reset, exact fix-up launch).
+    paired = w.T == 128 and 4 * w.B <= torch.cuda.get_device_properties(dev).multi_processor_count
+    roofline = {"bound": "hbm", "kernel": "pair_marginal_kernel" if paired else "chain_marginal_kernel",
+                "achieved": achieved, "peak": HBM_PEAK_GBPS,
                 "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS, "traffic": stored_traffic(w.key),
                 "algorithmic_bytes_per_launch": alg_bytes, "avg_launch_ms": pass2_avg,
                 "whole_call": {"algorithmic_bytes": call_bytes, "avg_ms": sum(whole) / len(whole),
