@@ -59,7 +59,10 @@ typedef enum {
     LCCRF_ALGO_SEQUENTIAL = 1, /* position by position (the forward algorithm as the paper uses it), one
                                   workgroup per chain; AUTO may instead split a chain over two workgroups */
     LCCRF_ALGO_SCAN = 2,       /* chunked associative scan over positions (the parallel variant the
-                                  paper cites in "Sequence Tagging"); only where implemented */
+                                  paper cites in "Sequence Tagging"): products of the T x T matrices
+                                  of each chunk, a short serial pass over chunks, then every chunk
+                                  on its own.  Sum queries with T <= 16 only, else LCCRF_ENOTIMPL;
+                                  AUTO takes it for long chains in small batches */
     LCCRF_ALGO_SEQUENTIAL_EXACT = 3 /* sequential, and every log-sum-exp shifted by its own maximum:
                                   the step that normally only replays rejected speculative steps
                                   is used for every position (same results up to rounding; slower) */
@@ -142,6 +145,12 @@ int lccrf_marginals_timed(const void* phi, lccrf_dtype dt, const int32_t* length
                           int B, int N, int T, float* logZ, float* marginals,
                           void* workspace, size_t workspace_bytes, void* stream, lccrf_algo algo,
                           void* ev_begin, void* ev_between, void* ev_end);
+
+/* Positions per chunk of LCCRF_ALGO_SCAN: a process-wide tuning knob (default 64; 0 restores the
+ * default; values outside [4, 4096] return LCCRF_EINVAL and change nothing).  It enters
+ * lccrf_workspace_bytes, so set it before sizing a workspace, and not while another thread is
+ * inside a query.  Results do not depend on it beyond rounding. */
+int lccrf_set_scan_chunk(int chunk);
 
 /* Static, human-readable text for a status code. */
 const char* lccrf_strerror(int code);

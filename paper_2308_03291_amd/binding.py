@@ -30,7 +30,7 @@ MAX_T = 256
 EXPORTS = (
     "lccrf_workspace_bytes", "lccrf_log_partition", "lccrf_marginals", "lccrf_argmax",
     "lccrf_log_partition_algo", "lccrf_marginals_algo", "lccrf_argmax_algo",
-    "lccrf_marginals_timed", "lccrf_strerror", "lccrf_version",
+    "lccrf_marginals_timed", "lccrf_set_scan_chunk", "lccrf_strerror", "lccrf_version",
 )
 
 _lib = None
@@ -67,12 +67,19 @@ def load_library() -> ctypes.CDLL:
     lib.lccrf_strerror.argtypes = [i]
     lib.lccrf_strerror.restype = ctypes.c_char_p
     lib.lccrf_version.argtypes = []
+    lib.lccrf_set_scan_chunk.argtypes = [i]
+    lib.lccrf_set_scan_chunk.restype = i
     _lib = lib
     return lib
 
 
 def strerror(code: int) -> str:
     return load_library().lccrf_strerror(int(code)).decode()
+
+
+def set_scan_chunk(chunk: int) -> None:
+    """Positions per chunk of ALGO_SCAN (0: default).  Size workspaces after calling this."""
+    _check(load_library().lccrf_set_scan_chunk(int(chunk)), "lccrf_set_scan_chunk")
 
 
 def _check(rc: int, what: str):

@@ -8,8 +8,14 @@ namespace {
 constexpr size_t kAlign = 256;
 inline size_t round_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 
+// Positions per chunk of the chunked scan (lccrf_set_scan_chunk).
+constexpr int kDefaultScanChunk = 64;
+int g_scan_chunk = kDefaultScanChunk;
+
 struct SumWorkspace {
-    size_t ua, ub, Oa, Ob, mail, failed, total;
+    size_t ua, ub, Oa, Ob, mail, failed;
+    size_t Pl, rel, base, Fv, OF, Gv, OG;  // chunked scan (T <= 16 only, else empty)
+    size_t total;
 };
 inline SumWorkspace sum_workspace(size_t B, size_t N, size_t T) {
     SumWorkspace w;
@@ -20,6 +26,14 @@ inline SumWorkspace sum_workspace(size_t B, size_t N, size_t T) {
     w.Ob = off; off += round_up(B * N * sizeof(double));
     w.mail = off; off += round_up(lccrf::pair_mail_words((int)B) * sizeof(unsigned long long));
     w.failed = off; off += round_up(B * sizeof(int));
+    const size_t BC = lccrf::scan_supported((int)T) ? B * ((N + g_scan_chunk - 1) / g_scan_chunk) : 0;
+    w.Pl = off; off += round_up(BC * 256 * sizeof(float));
+    w.rel = off; off += round_up(BC * 16 * sizeof(float));
+    w.base = off; off += round_up(BC * sizeof(double));
+    w.Fv = off; off += round_up(BC * T * sizeof(float));
+    w.OF = off; off += round_up(BC * sizeof(double));
+    w.Gv = off; off += round_up(BC * T * sizeof(float));
+    w.OG = off; off += round_up(BC * sizeof(double));
     w.total = off;
     return w;
 }
@@ -43,6 +57,12 @@ int check_common(const void* phi, int dt, int B, int N, int T, const void* ws, s
     return LCCRF_OK;
 }
 
+// Whether LCCRF_ALGO_AUTO takes the chunked scan: the tag set fits its kernels, the chains are long
+// enough for the serial depth to dominate, and the batch alone would not fill the chip.
+inline bool scan_pays(int B, int N, int T) {
+    return lccrf::scan_supported(T) && N >= 8 * g_scan_chunk && (long long)B * N <= (1ll << 22);
+}
+
 int sum_query(int op, const void* phi, int dt, const int32_t* lengths, int B, int N, int T, float* logZ,
               float* marginals, void* workspace, size_t workspace_bytes, void* stream, int algo,
               void* ev_begin = nullptr, void* ev_between = nullptr, void* ev_end = nullptr) {
@@ -54,11 +74,31 @@ int sum_query(int op, const void* phi, int dt, const int32_t* lengths, int B, in
     if (op == 1 && !marginals) return LCCRF_ENULL;
     if ((logZ && !aligned_to(logZ, 4)) || (marginals && !aligned_to(marginals, 16))) return LCCRF_EALIGN;
     if (lengths && !aligned_to(lengths, 4)) return LCCRF_EALIGN;
-    if (algo == LCCRF_ALGO_SCAN) return LCCRF_ENOTIMPL;
+    if (algo == LCCRF_ALGO_SCAN && !lccrf::scan_supported(T)) return LCCRF_ENOTIMPL;
     const SumWorkspace w = sum_workspace(B, N, T);
     char* base = static_cast<char*>(workspace);
     hipStream_t st = static_cast<hipStream_t>(stream);
     if (ev_begin && hipEventRecord(static_cast<hipEvent_t>(ev_begin), st) != hipSuccess) return LCCRF_ELAUNCH;
+    if (algo == LCCRF_ALGO_SCAN || (algo == LCCRF_ALGO_AUTO && scan_pays(B, N, T))) {
+        float* Fv = reinterpret_cast<float*>(base + w.Fv);
+        double* OF = reinterpret_cast<double*>(base + w.OF);
+        float* Gv = reinterpret_cast<float*>(base + w.Gv);
+        double* OG = reinterpret_cast<double*>(base + w.OG);
+        hipError_t e = lccrf::launch_scan_boundaries(dt, phi, lengths, B, N, T, g_scan_chunk,
+                                                     reinterpret_cast<float*>(base + w.Pl),
+                                                     reinterpret_cast<float*>(base + w.rel),
+                                                     reinterpret_cast<double*>(base + w.base), Fv, OF, Gv, OG, logZ,
+                                                     op == 1, st);
+        if (e == hipSuccess && op == 1)
+            e = lccrf::launch_chunked_marginals(dt, phi, lengths, B, N, T, reinterpret_cast<float*>(base + w.ua),
+                                                reinterpret_cast<float*>(base + w.ub),
+                                                reinterpret_cast<double*>(base + w.Oa),
+                                                reinterpret_cast<double*>(base + w.Ob), marginals, g_scan_chunk, Fv,
+                                                OF, Gv, OG, st, static_cast<hipEvent_t>(ev_between), false);
+        if (e != hipSuccess) return LCCRF_ELAUNCH;
+        if (ev_end && hipEventRecord(static_cast<hipEvent_t>(ev_end), st) != hipSuccess) return LCCRF_ELAUNCH;
+        return LCCRF_OK;
+    }
     const hipError_t e = lccrf::launch_sequential_sum(
         op, dt, phi, lengths, B, N, T, reinterpret_cast<float*>(base + w.ua), reinterpret_cast<float*>(base + w.ub),
         reinterpret_cast<double*>(base + w.Oa), reinterpret_cast<double*>(base + w.Ob), logZ, marginals, st,
@@ -148,6 +188,13 @@ const char* lccrf_strerror(int code) {
     }
 }
 
-int lccrf_version(void) { return 100; }
+int lccrf_set_scan_chunk(int chunk) {
+    if (chunk == 0) chunk = kDefaultScanChunk;
+    if (chunk < 4 || chunk > 4096) return LCCRF_EINVAL;
+    g_scan_chunk = chunk;
+    return LCCRF_OK;
+}
+
+int lccrf_version(void) { return 101; }
 
 }  // extern "C"

@@ -353,34 +353,44 @@ struct ChainArgs {
     float* mu;
     int exact_only;  // 1: never take the speculative step (tests)
     const int* only_failed;  // second pass: if set, recompute only the sequences flagged here
+    // Chunked schedule (chunk > 0): workgroup pair v serves chunk c = v % C of sequence v / C, the
+    // tag positions [c chunk, (c+1) chunk), as a chain of its own that starts one position earlier
+    // from the boundary vectors the scan has produced (lccrf_scan.hip).
+    int chunk, C;
+    const float* Fv;   // [B][C][T] alpha at the last position of each chunk, normalised
+    const double* OF;  // [B][C] its offset
+    const float* Gv;   // [B][C][T] beta at the last position of each chunk, normalised
+    const double* OG;  // [B][C]
 };
 
-// Walks positions first, first+dir, ..., last (dir = +1 or -1) with a ring of PF tiles:
-// `load(i, slot)` issues the loads of position i into ring slot `slot`; `step(i, slot)`
-// consumes the slot, which is refilled with the tile PF positions ahead right after.
-//
-// Every refill is issued unconditionally (past the end of the walk the last position is
-// simply loaded again and never used).  That costs PF redundant tile loads per chain and buys
-// a loop in which the number of loads issued after any tile is the same on every path, which
-// is what lets the compiler wait for exactly the oldest tile (s_waitcnt vmcnt(n) with n > 0)
-// and keep the PF - 1 younger ones in flight.
-template <int PF, typename Load, typename Step>
-__device__ __forceinline__ void walk(int first, int last, int dir, Load load, Step step) {
-    const int n = (last - first) * dir + 1;  // number of positions (<= 0: nothing to do)
-    if (n <= 0) return;
-#pragma unroll
-    for (int p = 0; p < PF; ++p) load(first + (p < n ? p : n - 1) * dir, p);
-    int done = 0;
-    while (true) {
-#pragma unroll
-        for (int p = 0; p < PF; ++p) {
-            const int i = first + done * dir;
-            step(i, p);
-            const int ahead = done + PF;
-            load(first + (ahead < n ? ahead : n - 1) * dir, p);
-            if (++done >= n) return;
-        }
+// The stretch of positions one pair of workgroups handles: all of a sequence, or one chunk.
+struct Span {
+    int b, c;
+    int L;       // clamped length of the sequence
+    int p0, e;   // first and last position of the chain (p0 carries the start vector)
+    bool first;  // p0 is position 0: start from the first row of the first matrix
+    bool last;   // e is the last position of the sequence: beta = 0 there
+    bool empty;  // nothing to do
+};
+
+__device__ __forceinline__ Span make_span(const ChainArgs& a, int v) {
+    Span s;
+    if (a.chunk <= 0) {
+        s.b = v; s.c = 0;
+        s.L = clamp_length(a.lengths, s.b, a.N);
+        s.p0 = 0; s.e = s.L - 1; s.first = true; s.last = true; s.empty = s.L == 0;
+    } else {
+        s.b = v / a.C; s.c = v % a.C;
+        s.L = clamp_length(a.lengths, s.b, a.N);
+        const int t0 = s.c * a.chunk;
+        s.empty = t0 >= s.L;
+        s.first = s.c == 0;
+        s.p0 = s.first ? 0 : t0 - 1;
+        const int t1 = t0 + a.chunk;
+        s.e = (t1 < s.L ? t1 : s.L) - 1;
+        s.last = s.e == s.L - 1;
     }
+    return s;
 }
 
 // One position of a forward chain: speculative step, exact replay if it was rejected.
@@ -423,11 +433,13 @@ __global__ __launch_bounds__(G::W) void chain_half_kernel(ChainArgs a) {
     __shared__ ChainSmem<G> sm;
     constexpr int ITEMS = G::ITEMS;
     const int tid = threadIdx.x;
-    const int b = blockIdx.x >> 1, dir = blockIdx.x & 1;
+    const int dir = blockIdx.x & 1;
+    const Span sp = make_span(a, blockIdx.x >> 1);
+    const int b = sp.b;
     const int N = a.N, T = a.T;
-    const int L = clamp_length(a.lengths, b, N);
-    if (L == 0) return;
-    const int h = L / 2;
+    if (sp.empty) return;
+    const int p0 = sp.p0, e = sp.e;
+    const int h = p0 + (e - p0 + 1) / 2;
     const int c4 = 4 * (tid % G::LPR), r0 = tid / G::LPR;
     const TIN* phib = static_cast<const TIN*>(a.phi) + (size_t)b * N * T * T;
     const size_t TT = (size_t)T * T;
@@ -446,9 +458,12 @@ __global__ __launch_bounds__(G::W) void chain_half_kernel(ChainArgs a) {
     auto load = [&](int i, int slot) { load_tile<G, TIN, ALIGNED>(phib + (size_t)i * TT, T, c4, r0, ring[slot]); };
 
     if (dir == 0) {
-        publish_columns<G>(sm, 0, tid, (tid < T) ? Elem<TIN>::get(phib + tid) * kLog2e : LCCRF_NEG_INF);
+        float v0 = LCCRF_NEG_INF;
+        if (tid < T) v0 = sp.first ? Elem<TIN>::get(phib + tid) * kLog2e : a.Fv[((size_t)b * a.C + sp.c - 1) * T + tid];
+        if (!sp.first) O = a.OF[(size_t)b * a.C + sp.c - 1];
+        publish_columns<G>(sm, 0, tid, v0);
         __syncthreads();
-        walk<PF>(1, h, +1, load, [&](int i, int slot) {
+        walk<PF>(p0 + 1, h, +1, load, [&](int i, int slot) {
             const float d = read_shift<G>(sm, buf);
             O += (double)d;
             float ua[ITEMS];
@@ -466,9 +481,12 @@ __global__ __launch_bounds__(G::W) void chain_half_kernel(ChainArgs a) {
         if (tid < T) a.ua[(vb + h) * T + tid] = sm.rvec[buf][tid] - d;
         if (tid == 0) a.Oa[vb + h] = O;
     } else {
-        publish_columns<G>(sm, 0, tid, (tid < T) ? 0.f : LCCRF_NEG_INF);
+        float v0 = LCCRF_NEG_INF;
+        if (tid < T) v0 = sp.last ? 0.f : a.Gv[((size_t)b * a.C + sp.c) * T + tid];
+        if (!sp.last) O = a.OG[(size_t)b * a.C + sp.c];
+        publish_columns<G>(sm, 0, tid, v0);
         __syncthreads();
-        walk<PF>(L - 1, h + 1, -1, load, [&](int i, int slot) {
+        walk<PF>(e, h + 1, -1, load, [&](int i, int slot) {
             const float d = read_shift<G>(sm, buf);
             O += (double)d;
             const float4 q = *reinterpret_cast<const float4*>(&sm.rvec[buf][c4]);
@@ -517,9 +535,11 @@ __global__ __launch_bounds__(G::W) void chain_marginal_kernel(ChainArgs a) {
     __shared__ ChainSmem<G> sm;
     constexpr int ITEMS = G::ITEMS;
     const int tid = threadIdx.x;
-    const int b = blockIdx.x >> 1, dir = blockIdx.x & 1;
+    const int dir = blockIdx.x & 1;
+    const Span sp = make_span(a, blockIdx.x >> 1);
+    const int b = sp.b;
     const int N = a.N, T = a.T;
-    const int L = clamp_length(a.lengths, b, N);
+    const int L = sp.L;
     const size_t TT = (size_t)T * T;
     const size_t vb = (size_t)b * N;
     float* mub = a.mu + (size_t)b * N * TT;
@@ -527,8 +547,10 @@ __global__ __launch_bounds__(G::W) void chain_marginal_kernel(ChainArgs a) {
     if (a.only_failed && a.only_failed[b] == 0) return;  // the paired pass has done this sequence
 
     if (dir == 0) {
-        // positions past the end carry no edge: their marginals are zero
-        const size_t z0 = (size_t)L * TT, z1 = (size_t)N * TT;
+        // positions past the end carry no edge: their marginals are zero (a chunk clears its own range)
+        const int zfrom = a.chunk > 0 ? (sp.c * a.chunk > L ? sp.c * a.chunk : L) : L;
+        const int zto = a.chunk > 0 ? ((sp.c + 1) * a.chunk < N ? (sp.c + 1) * a.chunk : N) : N;
+        const size_t z0 = (size_t)zfrom * TT, z1 = (size_t)(zto > zfrom ? zto : zfrom) * TT;
         if (ALIGNED) {
             float4* p = reinterpret_cast<float4*>(mub);
             for (size_t k = z0 / 4 + tid; k < z1 / 4; k += G::W) p[k] = make_float4(0.f, 0.f, 0.f, 0.f);
@@ -537,17 +559,19 @@ __global__ __launch_bounds__(G::W) void chain_marginal_kernel(ChainArgs a) {
         }
     }
     if (L == 0) {
-        if (dir == 0 && tid == 0 && a.logZ) a.logZ[b] = 0.f;
+        if (dir == 0 && sp.c == 0 && tid == 0 && a.logZ) a.logZ[b] = 0.f;
         return;
     }
-    const int h = L / 2;
+    if (sp.empty) return;
+    const int p0 = sp.p0, e = sp.e;
+    const int h = p0 + (e - p0 + 1) / 2;
     const int c4 = 4 * (tid % G::LPR), r0 = tid / G::LPR;
     const TIN* phib = static_cast<const TIN*>(a.phi) + (size_t)b * N * TT;
 
     smem_init<G>(sm, tid);
     const double lz2 = midpoint_log2z<G>(sm, a, vb, h, T, tid);
     const bool feasible = lz2 > -1.0e300;  // false: no path has a finite score, marginals are 0
-    if (dir == 0 && tid == 0 && a.logZ) a.logZ[b] = (float)(lz2 * kLn2);
+    if (dir == 0 && sp.c == 0 && tid == 0 && a.logZ) a.logZ[b] = (float)(lz2 * kLn2);
 
     float ring[PF][ITEMS][4];
     int buf = 0, nstep = 0;
@@ -565,7 +589,7 @@ __global__ __launch_bounds__(G::W) void chain_marginal_kernel(ChainArgs a) {
             for (int j = 0; j < 4; ++j) aux[slot][j] = a.ub[(vb + i) * T + (c4 + j < T ? c4 + j : T - 1)];
             ob[slot] = a.Ob[vb + i];
         };
-        walk<PF>(h + 1, L - 1, +1, load, [&](int i, int slot) {
+        walk<PF>(h + 1, e, +1, load, [&](int i, int slot) {
             const float d = read_shift<G>(sm, buf);
             kappa += read_drift<G>(sm, buf);
             O += (double)d;
@@ -597,7 +621,7 @@ __global__ __launch_bounds__(G::W) void chain_marginal_kernel(ChainArgs a) {
             }
             oa[slot] = a.Oa[vb + i - 1];
         };
-        walk<PF>(h, 1, -1, load, [&](int i, int slot) {
+        walk<PF>(h, p0 + 1, -1, load, [&](int i, int slot) {
             const float d = read_shift<G>(sm, buf);
             kappa += read_drift<G>(sm, buf);
             O += (double)d;
@@ -611,6 +635,7 @@ __global__ __launch_bounds__(G::W) void chain_marginal_kernel(ChainArgs a) {
                                           mub + (size_t)i * TT);
         });
         // position 0: p(y_0 = t) = softmax_t(alpha_0(t) + beta_0(t)) in row 0, zeros elsewhere
+        if (!sp.first) return;
         for (int k = T + tid; k < (int)TT; k += G::W) mub[k] = 0.f;
         if (tid < 64) {
             float m = LCCRF_NEG_INF;
@@ -659,7 +684,7 @@ struct PairPlan {
 
 template <typename G, typename TIN, bool ALIGNED, int PF1, int PF2>
 static hipError_t launch_geo(int op, ChainArgs a, hipStream_t st, hipEvent_t between, const PairPlan& pair) {
-    hipLaunchKernelGGL((chain_half_kernel<G, TIN, ALIGNED, PF1>), dim3(2 * a.B), dim3(G::W), 0, st, a);
+    hipLaunchKernelGGL((chain_half_kernel<G, TIN, ALIGNED, PF1>), dim3(2 * a.B * a.C), dim3(G::W), 0, st, a);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     if (between) {
@@ -679,7 +704,7 @@ static hipError_t launch_geo(int op, ChainArgs a, hipStream_t st, hipEvent_t bet
         if (e != hipSuccess) return e;
         a.only_failed = pair.failed;
     }
-    hipLaunchKernelGGL((chain_marginal_kernel<G, TIN, ALIGNED, PF2>), dim3(2 * a.B), dim3(G::W), 0, st, a);
+    hipLaunchKernelGGL((chain_marginal_kernel<G, TIN, ALIGNED, PF2>), dim3(2 * a.B * a.C), dim3(G::W), 0, st, a);
     return hipGetLastError();
 }
 
@@ -700,7 +725,7 @@ hipError_t launch_sequential_sum(int op, int dtype, const void* phi, const int32
                                  float* ua, float* ub, double* Oa, double* Ob, float* logZ, float* mu,
                                  hipStream_t st, hipEvent_t between, bool exact_only, unsigned long long* mail,
                                  int* failed) {
-    ChainArgs a{phi, lengths, B, N, T, ua, ub, Oa, Ob, logZ, mu, exact_only ? 1 : 0, nullptr};
+    ChainArgs a{phi, lengths, B, N, T, ua, ub, Oa, Ob, logZ, mu, exact_only ? 1 : 0, nullptr, 0, 1, nullptr, nullptr, nullptr, nullptr};
     // Pairs pay off when one workgroup per chain would leave at least half of the chip idle.
     static const int cus = [] {
         int dev = 0, n = 0;
@@ -714,6 +739,21 @@ hipError_t launch_sequential_sum(int op, int dtype, const void* phi, const int32
         return aligned ? launch_T<float, true>(op, a, st, between, pair) : launch_T<float, false>(op, a, st, between, pair);
     return aligned ? launch_T<uint16_t, true>(op, a, st, between, pair)
                    : launch_T<uint16_t, false>(op, a, st, between, pair);
+}
+
+// Marginals of every chunk of every sequence from the boundary vectors of the scan: the same two
+// passes, one pair of workgroups per chunk.  logZ is not written here (the scan has it already).
+hipError_t launch_chunked_marginals(int dtype, const void* phi, const int32_t* lengths, int B, int N, int T,
+                                    float* ua, float* ub, double* Oa, double* Ob, float* mu, int chunk,
+                                    const float* Fv, const double* OF, const float* Gv, const double* OG,
+                                    hipStream_t st, hipEvent_t between, bool exact_only) {
+    const int C = (N + chunk - 1) / chunk;
+    ChainArgs a{phi, lengths, B, N, T, ua, ub, Oa, Ob, nullptr, mu, exact_only ? 1 : 0, nullptr, chunk, C, Fv, OF, Gv, OG};
+    const PairPlan pair{nullptr, nullptr, dtype};
+    const bool aligned = (T % 4) == 0;
+    if (dtype == 0)
+        return aligned ? launch_T<float, true>(1, a, st, between, pair) : launch_T<float, false>(1, a, st, between, pair);
+    return aligned ? launch_T<uint16_t, true>(1, a, st, between, pair) : launch_T<uint16_t, false>(1, a, st, between, pair);
 }
 
 }  // namespace lccrf

@@ -182,6 +182,34 @@ __device__ __forceinline__ float xor_sum(float x) {
     return x;
 }
 
+// Walks positions first, first+dir, ..., last (dir = +1 or -1) with a ring of PF tiles:
+// `load(i, slot)` issues the loads of position i into ring slot `slot`; `step(i, slot)`
+// consumes the slot, which is refilled with the tile PF positions ahead right after.
+//
+// Every refill is issued unconditionally (past the end of the walk the last position is
+// simply loaded again and never used).  That costs PF redundant tile loads per chain and buys
+// a loop in which the number of loads issued after any tile is the same on every path, which
+// is what lets the compiler wait for exactly the oldest tile (s_waitcnt vmcnt(n) with n > 0)
+// and keep the PF - 1 younger ones in flight.
+template <int PF, typename Load, typename Step>
+__device__ __forceinline__ void walk(int first, int last, int dir, Load load, Step step) {
+    const int n = (last - first) * dir + 1;  // number of positions (<= 0: nothing to do)
+    if (n <= 0) return;
+#pragma unroll
+    for (int p = 0; p < PF; ++p) load(first + (p < n ? p : n - 1) * dir, p);
+    int done = 0;
+    while (true) {
+#pragma unroll
+        for (int p = 0; p < PF; ++p) {
+            const int i = first + done * dir;
+            step(i, p);
+            const int ahead = done + PF;
+            load(first + (ahead < n ? ahead : n - 1) * dir, p);
+            if (++done >= n) return;
+        }
+    }
+}
+
 __device__ __forceinline__ float finite_or_zero(float m) { return (m == LCCRF_NEG_INF) ? 0.0f : m; }
 
 __device__ __forceinline__ int clamp_length(const int32_t* __restrict__ lengths, int b, int N) {

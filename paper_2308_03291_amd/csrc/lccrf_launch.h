@@ -27,6 +27,20 @@ hipError_t launch_pair_marginals(int dtype, const void* phi, const int32_t* leng
                                  const float* ua, const float* ub, const double* Oa, const double* Ob,
                                  float* logZ, float* mu, unsigned long long* mail, int* failed, hipStream_t st);
 
+// Chunked scan over positions (lccrf_scan.hip), tag sets of at most 16.  Writes, per chunk of `chunk`
+// positions (C = ceil(N / chunk) chunks per sequence), the chunk's transfer matrix (Pl: 256 floats, rel: 16
+// floats, base: 1 double) and alpha / beta at the chunk's last position (Fv, Gv: T floats; OF, OG: 1
+// double), and logZ if non-null.  with_beta false: forward vectors and logZ only.
+bool scan_supported(int T);
+hipError_t launch_scan_boundaries(int dtype, const void* phi, const int32_t* lengths, int B, int N, int T, int chunk,
+                                  float* Pl, float* rel, double* base, float* Fv, double* OF, float* Gv, double* OG,
+                                  float* logZ, bool with_beta, hipStream_t st);
+// Two-pass forward-backward inside every chunk from those boundary vectors (lccrf_chain.hip); chunk >= 4.
+hipError_t launch_chunked_marginals(int dtype, const void* phi, const int32_t* lengths, int B, int N, int T,
+                                    float* ua, float* ub, double* Oa, double* Ob, float* mu, int chunk,
+                                    const float* Fv, const double* OF, const float* Gv, const double* OG,
+                                    hipStream_t st, hipEvent_t between, bool exact_only);
+
 // Max-plus chain with back-pointers and back-trace.  bp: [B][N][T] bytes of scratch.
 hipError_t launch_sequential_max(int dtype, const void* phi, const int32_t* lengths, int B, int N, int T,
                                  uint8_t* bp, float* best_score, int32_t* tags, hipStream_t st);

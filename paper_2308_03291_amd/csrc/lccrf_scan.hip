@@ -1,0 +1,308 @@
+// Chunked log-semiring scan over the positions of long chains with a small tag set (T <= 16).
+//
+// The paper (section "Sequence Tagging") notes that the forward algorithm can also be run as a
+// parallel scan over products of T x T matrices, at T times the arithmetic of the sequential
+// recursion, which pays when T is much smaller than the length.  Here the scan is a three-phase
+// chunked one sized for one GPU:
+//
+//   phase A (chunk_product_kernel, one wave per chunk of `chunk` positions, all chunks at once):
+//       P_c = phi_first (x) ... (x) phi_last, the log-semiring product of the chunk's matrices,
+//       P_c[r][s] = log sum over paths that enter the chunk from tag r and leave it in tag s;
+//   phase B (chunk_boundary_kernel, two waves per sequence, serial over the chunks only):
+//       alpha at the last position of every chunk (F_c = F_{c-1} (x) P_c) and beta at the last
+//       position of every chunk (G_{c-1} = P_c (x) G_c), and logZ from the last F;
+//   phase C (the chain kernels of lccrf_chain.hip, one pair of workgroups per chunk):
+//       the ordinary two-chain forward-backward inside every chunk, started from F and G.
+//
+// Phase A keeps each product in the linear domain, scaled per entry tag by an exact power of
+// two after every position, so that one position costs T^2 exponentials and four
+// v_mfma_f32_16x16x4_f32 instead of T^3 exponentials.  A product is accepted only if no entry
+// that is not structurally zero ever fell below 2^-60 of its scale (then no term that matters
+// was flushed to zero); otherwise the wave recomputes its chunk with the exact log-domain
+// product, every log-sum-exp shifted by its own maximum.  Both forms write the same format:
+// log2 of the scaled product, one integer log2 scale per entry tag and one common offset.
+#include "lccrf_device.h"
+#include "lccrf_launch.h"
+
+namespace lccrf {
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+constexpr float kTiny = 0x1p-60f;
+constexpr int kScanPF = 8;
+
+struct ScanArgs {
+    const void* phi;
+    const int32_t* lengths;
+    int B, N, T;
+    int chunk, C;
+    // log2 P_c[r][s] = Pl[b][c][s][r] + rel[b][c][r] + base[b][c]   (r: entry tag, s: exit tag;
+    // tags >= T are padded with -inf)
+    float* Pl;     // [B][C][16][16]
+    float* rel;    // [B][C][16]  integer valued, <= 0
+    double* base;  // [B][C]
+    float* Fv;     // [B][C][T]   alpha at the last position of chunk c, maximum 0 ...
+    double* OF;    // [B][C]      ... plus this offset (base-2 logarithms)
+    float* Gv;     // [B][C][T]   beta at the last position of chunk c
+    double* OG;    // [B][C]
+    float* logZ;   // [B] or null
+    int with_beta;
+};
+
+// First and last position whose matrix belongs to chunk c (first > last: none).
+__device__ __forceinline__ void chunk_range(int c, int chunk, int L, int& first, int& last) {
+    const int t0 = c * chunk, t1 = t0 + chunk;
+    first = c == 0 ? 1 : t0;
+    last = (t1 < L ? t1 : L) - 1;
+}
+
+// ---------------------------------------------------------------------------------------
+// Phase A.
+template <typename TIN>
+__global__ __launch_bounds__(64) void chunk_product_kernel(ScanArgs a) {
+    __shared__ float Pc[16][17];
+    __shared__ float Ph[16][17];
+    const int lane = threadIdx.x;
+    const int b = blockIdx.x / a.C, c = blockIdx.x % a.C;
+    const int T = a.T, N = a.N;
+    const int L = clamp_length(a.lengths, b, N);
+    if (c * a.chunk >= L) return;
+    int first, last;
+    chunk_range(c, a.chunk, L, first, last);
+    const size_t TT = (size_t)T * T;
+    const TIN* phib = static_cast<const TIN*>(a.phi) + (size_t)b * N * TT;
+    float* Pout = a.Pl + ((size_t)b * a.C + c) * 256;
+    float* rel_out = a.rel + ((size_t)b * a.C + c) * 16;
+    double* base_out = a.base + (size_t)b * a.C + c;
+
+    // ---- linear-domain product on the matrix cores.
+    // D[s][r] (exit tag s, entry tag r) sits in the accumulator layout of the 16x16x4 MFMA:
+    // lane (g = lane / 16, j = lane % 16) holds D[4g + v][j], v = 0..3.  The same lane loads
+    // phi_i[4g + v][j]; as the A operand of MFMA number v that is E^T[j][k = g] for the inner
+    // index s = 4g + v, and D's own register v is the matching B operand, so
+    //     D_new[t][r] = sum_v sum_g E[4g + v][t] D[4g + v][r] = sum_s E[s][t] D[s][r]
+    // needs no data movement between positions.
+    {
+        const int g = lane >> 4, j = lane & 15;
+        int off[4];
+        bool in[4];
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+            const int s = 4 * g + v;
+            in[v] = s < T && j < T;
+            off[v] = (s < T ? s : T - 1) * T + (j < T ? j : T - 1);
+        }
+        float D[4];
+#pragma unroll
+        for (int v = 0; v < 4; ++v) D[v] = (4 * g + v == j) ? 1.f : 0.f;
+        float ring[kScanPF][4];
+        auto load = [&](int i, int slot) {
+            const TIN* m = phib + (size_t)i * TT;
+#pragma unroll
+            for (int v = 0; v < 4; ++v) ring[slot][v] = Elem<TIN>::get(m + off[v]);
+        };
+        double Msum = 0.0;
+        int esum = 0;
+        bool bad = false;
+        walk<kScanPF>(first, last, +1, load, [&](int, int slot) {
+            float x[4];
+#pragma unroll
+            for (int v = 0; v < 4; ++v) x[v] = in[v] ? ring[slot][v] * kLog2e : LCCRF_NEG_INF;
+            const float m = finite_or_zero(xor_max<1, 64>(fmaxf(fmaxf(x[0], x[1]), fmaxf(x[2], x[3]))));
+            Msum += (double)m;
+            f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const float E = ex2(x[v] - m);
+                bad |= (E < kTiny) & (x[v] > LCCRF_NEG_INF);
+                acc = __builtin_amdgcn_mfma_f32_16x16x4f32(E, D[v], acc, 0, 0, 0);
+            }
+            // power-of-two rescale of each entry tag's column (exact)
+            const float cm = xor_max<16, 64>(fmaxf(fmaxf(acc[0], acc[1]), fmaxf(acc[2], acc[3])));
+            const int ex = cm > 0.f ? ((__float_as_int(cm) >> 23) & 0xff) - 127 : 0;
+            const float sc = __int_as_float((127 - ex) << 23);
+            esum += ex;
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                D[v] = acc[v] * sc;
+                bad |= (D[v] != 0.f) & !(D[v] >= kTiny);
+            }
+        });
+        if (__builtin_amdgcn_ballot_w64(bad) == 0) {
+            const float ef = j < T ? (float)esum : LCCRF_NEG_INF;
+            const float emax = finite_or_zero(xor_max<1, 16>(ef));
+#pragma unroll
+            for (int v = 0; v < 4; ++v) Pout[(4 * g + v) * 16 + j] = (in[v] && D[v] > 0.f) ? lg2(D[v]) : LCCRF_NEG_INF;
+            if (g == 0) rel_out[j] = ef - emax;
+            if (lane == 0) *base_out = Msum + (double)emax;
+            return;
+        }
+    }
+
+    // ---- exact log-domain product (rare).  Lane (r = lane / 4, q = lane % 4) owns
+    // P[r][4q .. 4q+3]; P and the current matrix are exchanged through LDS.
+    {
+        const int r = lane >> 2, q = lane & 3;
+        float out[4];
+#pragma unroll
+        for (int jj = 0; jj < 4; ++jj) out[jj] = (r == 4 * q + jj) ? 0.f : LCCRF_NEG_INF;
+        float sg = 0.f;  // integer valued
+        for (int i = first; i <= last; ++i) {
+            __syncthreads();
+#pragma unroll
+            for (int jj = 0; jj < 4; ++jj) {
+                const int t = 4 * q + jj;
+                Pc[r][t] = out[jj];
+                Ph[r][t] = (r < T && t < T) ? Elem<TIN>::get(phib + (size_t)i * TT + r * T + t) * kLog2e : LCCRF_NEG_INF;
+            }
+            __syncthreads();
+            float mx[4] = {LCCRF_NEG_INF, LCCRF_NEG_INF, LCCRF_NEG_INF, LCCRF_NEG_INF};
+            for (int s = 0; s < 16; ++s) {
+                const float p = Pc[r][s];
+#pragma unroll
+                for (int jj = 0; jj < 4; ++jj) mx[jj] = fmaxf(mx[jj], p + Ph[s][4 * q + jj]);
+            }
+            float sm[4] = {0.f, 0.f, 0.f, 0.f};
+            for (int s = 0; s < 16; ++s) {
+                const float p = Pc[r][s];
+#pragma unroll
+                for (int jj = 0; jj < 4; ++jj) sm[jj] += ex2(p + Ph[s][4 * q + jj] - finite_or_zero(mx[jj]));
+            }
+#pragma unroll
+            for (int jj = 0; jj < 4; ++jj) out[jj] = mx[jj] + lg2(sm[jj]);
+            // shift the row by the integer part of its maximum: scales stay integers, hence exact
+            const float rm = xor_max<1, 4>(fmaxf(fmaxf(out[0], out[1]), fmaxf(out[2], out[3])));
+            const float sh = floorf(finite_or_zero(rm));
+            sg += sh;
+#pragma unroll
+            for (int jj = 0; jj < 4; ++jj) out[jj] -= sh;
+        }
+        const float ef = r < T ? sg : LCCRF_NEG_INF;
+        const float emax = finite_or_zero(xor_max<4, 64>(ef));
+#pragma unroll
+        for (int jj = 0; jj < 4; ++jj) {
+            const int t = 4 * q + jj;
+            Pout[t * 16 + r] = (r < T && t < T) ? out[jj] : LCCRF_NEG_INF;
+        }
+        if (q == 0) rel_out[r] = ef - emax;
+        if (lane == 0) *base_out = (double)emax;
+    }
+}
+
+// ---------------------------------------------------------------------------------------
+// Phase B.  Workgroup 2b runs the forward vector of sequence b through its chunk products,
+// workgroup 2b + 1 the backward vector.  Lane (o = lane / 4, q = lane % 4) produces output
+// entry o from the four input entries 4q .. 4q+3; the vector is passed from one step to the
+// next through LDS.
+template <typename TIN>
+__global__ __launch_bounds__(64) void chunk_boundary_kernel(ScanArgs a) {
+    __shared__ __attribute__((aligned(16))) float vec[2][16];
+    const int lane = threadIdx.x, o = lane >> 2, q = lane & 3;
+    const int b = blockIdx.x >> 1, dir = blockIdx.x & 1;
+    const int T = a.T, N = a.N;
+    const int L = clamp_length(a.lengths, b, N);
+    if (L == 0) {
+        if (dir == 0 && lane == 0 && a.logZ) a.logZ[b] = 0.f;
+        return;
+    }
+    if (dir == 1 && !a.with_beta) return;
+    const int Cb = (L + a.chunk - 1) / a.chunk;
+    const size_t cb = (size_t)b * a.C;
+    int buf = 0;
+    double O = 0.0;
+
+    if (dir == 0) {
+        const TIN* phib = static_cast<const TIN*>(a.phi) + (size_t)b * N * T * T;
+        float v = (lane < T) ? Elem<TIN>::get(phib + lane) * kLog2e : LCCRF_NEG_INF;  // alpha_0
+        float d = finite_or_zero(xor_max<1, 64>(v));
+        O = (double)d;
+        if (lane < 16) vec[0][lane] = v - d;
+        __syncthreads();
+        float pm[kScanPF][4], rl[kScanPF][4];
+        double bs[kScanPF];
+        auto load = [&](int c, int slot) {
+            const float4 p = *reinterpret_cast<const float4*>(a.Pl + (cb + c) * 256 + o * 16 + 4 * q);
+            const float4 e = *reinterpret_cast<const float4*>(a.rel + (cb + c) * 16 + 4 * q);
+            pm[slot][0] = p.x; pm[slot][1] = p.y; pm[slot][2] = p.z; pm[slot][3] = p.w;
+            rl[slot][0] = e.x; rl[slot][1] = e.y; rl[slot][2] = e.z; rl[slot][3] = e.w;
+            bs[slot] = a.base[cb + c];
+        };
+        float nv = v - d;
+        walk<kScanPF>(0, Cb - 1, +1, load, [&](int c, int slot) {
+            const float4 f = *reinterpret_cast<const float4*>(&vec[buf][4 * q]);
+            const float x0 = f.x + (pm[slot][0] + rl[slot][0]), x1 = f.y + (pm[slot][1] + rl[slot][1]);
+            const float x2 = f.z + (pm[slot][2] + rl[slot][2]), x3 = f.w + (pm[slot][3] + rl[slot][3]);
+            const float mx = xor_max<1, 4>(fmaxf(fmaxf(x0, x1), fmaxf(x2, x3)));
+            const float mf = finite_or_zero(mx);
+            const float s = xor_sum<1, 4>((ex2(x0 - mf) + ex2(x1 - mf)) + (ex2(x2 - mf) + ex2(x3 - mf)));
+            const float r = mx + lg2(s);
+            d = finite_or_zero(xor_max<4, 64>(r));
+            O += bs[slot] + (double)d;
+            nv = r - d;
+            buf ^= 1;
+            if (q == 0) {
+                vec[buf][o] = nv;
+                if (o < T) a.Fv[(cb + c) * T + o] = nv;
+            }
+            if (lane == 0) a.OF[cb + c] = O;
+            __syncthreads();
+        });
+        if (a.logZ) {
+            // the walk has run at least once (L >= 1): entry t sits in lanes 4t .. 4t+3, count it once
+            const float S = xor_sum<1, 64>(q == 0 ? ex2(nv) : 0.f);
+            if (lane == 0) a.logZ[b] = (float)((O + (double)lg2(S)) * kLn2);
+        }
+    } else {
+        if (lane < 16) vec[0][lane] = (lane < T) ? 0.f : LCCRF_NEG_INF;  // beta at the last position
+        __syncthreads();
+        float pm[kScanPF][4], rl[kScanPF];
+        double bs[kScanPF];
+        auto load = [&](int c, int slot) {
+            const float* P = a.Pl + (cb + c) * 256;
+#pragma unroll
+            for (int jj = 0; jj < 4; ++jj) pm[slot][jj] = P[(4 * q + jj) * 16 + o];
+            rl[slot] = a.rel[(cb + c) * 16 + o];
+            bs[slot] = a.base[cb + c];
+        };
+        walk<kScanPF>(Cb - 1, 1, -1, load, [&](int c, int slot) {
+            const float4 gq = *reinterpret_cast<const float4*>(&vec[buf][4 * q]);
+            const float x0 = pm[slot][0] + gq.x, x1 = pm[slot][1] + gq.y, x2 = pm[slot][2] + gq.z, x3 = pm[slot][3] + gq.w;
+            const float mx = xor_max<1, 4>(fmaxf(fmaxf(x0, x1), fmaxf(x2, x3)));
+            const float mf = finite_or_zero(mx);
+            const float s = xor_sum<1, 4>((ex2(x0 - mf) + ex2(x1 - mf)) + (ex2(x2 - mf) + ex2(x3 - mf)));
+            const float r = mx + lg2(s) + rl[slot];
+            const float d = finite_or_zero(xor_max<4, 64>(r));
+            O += bs[slot] + (double)d;
+            buf ^= 1;
+            if (q == 0) {
+                vec[buf][o] = r - d;
+                if (o < T) a.Gv[(cb + c - 1) * T + o] = r - d;
+            }
+            if (lane == 0) a.OG[cb + c - 1] = O;
+            __syncthreads();
+        });
+    }
+}
+
+// ---------------------------------------------------------------------------------------
+bool scan_supported(int T) { return T >= 1 && T <= 16; }
+
+hipError_t launch_scan_boundaries(int dtype, const void* phi, const int32_t* lengths, int B, int N, int T, int chunk,
+                                  float* Pl, float* rel, double* base, float* Fv, double* OF, float* Gv, double* OG,
+                                  float* logZ, bool with_beta, hipStream_t st) {
+    const int C = (N + chunk - 1) / chunk;
+    ScanArgs a{phi, lengths, B, N, T, chunk, C, Pl, rel, base, Fv, OF, Gv, OG, logZ, with_beta ? 1 : 0};
+    if (dtype == 0)
+        hipLaunchKernelGGL(chunk_product_kernel<float>, dim3(B * C), dim3(64), 0, st, a);
+    else
+        hipLaunchKernelGGL(chunk_product_kernel<uint16_t>, dim3(B * C), dim3(64), 0, st, a);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    if (dtype == 0)
+        hipLaunchKernelGGL(chunk_boundary_kernel<float>, dim3(2 * B), dim3(64), 0, st, a);
+    else
+        hipLaunchKernelGGL(chunk_boundary_kernel<uint16_t>, dim3(2 * B), dim3(64), 0, st, a);
+    return hipGetLastError();
+}
+
+}  // namespace lccrf

@@ -1,0 +1,123 @@
+"""GPU parity of the chunked scan schedule (ALGO_SCAN) against the CPU oracle, and against the
+sequential schedule: the scan regroups the same semiring products (associativity), so every
+result must agree to the tolerances of test_gpu_parity.py whatever the chunk size is."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2308_03291_amd import workloads
+from test_gpu_parity import check_case, crf  # noqa: F401  (fixture)
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture
+def chunk(crf):
+    """Sets the scan's chunk size for one test and restores the default afterwards."""
+    yield crf.set_scan_chunk
+    crf.set_scan_chunk(0)
+
+
+def _lens_around_chunks(N, k):
+    """Lengths that hit empty, one-position, chunk-aligned and ragged-tail cases."""
+    cand = [0, 1, 2, k - 1, k, k + 1, 2 * k, 2 * k + 1, N - 1, N]
+    return torch.tensor([min(max(c, 0), N) for c in cand], dtype=torch.int32)
+
+
+@pytest.mark.parametrize("k", [4, 7, 64])
+@pytest.mark.parametrize("T,N", [(1, 9), (2, 5), (5, 8), (5, 130), (13, 65), (16, 1), (16, 3), (16, 64), (16, 300)])
+def test_scan_fp32(crf, oracle_mod, chunk, T, N, k):
+    chunk(k)
+    lens = _lens_around_chunks(N, k)
+    phi, _ = workloads.random_case(5000 + 31 * T + N, len(lens), N, T, scale=1.5)
+    check_case(crf, oracle_mod, phi, lens, algo=crf.ALGO_SCAN, what=f"scan T={T} N={N} k={k}", queries=("logz", "mu"))
+
+
+@pytest.mark.parametrize("k", [4, 64])
+def test_scan_one_chunk_and_many_chunks(crf, oracle_mod, chunk, k):
+    """Degenerate chunk counts: the whole chain in one chunk (C = 1) and the smallest chunks."""
+    N = 64
+    chunk(k)
+    phi, lens = workloads.random_case(5100 + k, 6, N, 16, scale=2.0, ragged=True, min_len=1)
+    check_case(crf, oracle_mod, phi, lens, algo=crf.ALGO_SCAN, what=f"scan C={N // k}", queries=("logz", "mu"))
+
+
+def test_scan_bf16(crf, oracle_mod, chunk):
+    chunk(16)
+    phi, lens = workloads.random_case(5200, 5, 200, 16, scale=3.0, ragged=True, min_len=3, dtype="bf16")
+    check_case(crf, oracle_mod, phi, lens, poison=False, algo=crf.ALGO_SCAN, what="scan bf16", queries=("logz", "mu"))
+
+
+def test_scan_forbidden_edges_and_dead_chains(crf, oracle_mod, chunk):
+    """-inf potentials are structural zeros of the chunk products; a chain with no finite path
+    gives logZ = -inf and zero marginals."""
+    chunk(8)
+    T, N = 16, 50
+    phi, _ = workloads.random_case(5300, 5, N, T)
+    ninf = float("-inf")
+    phi[0, :, 3, :] = ninf                       # tag 3 can never be left
+    phi[1, 20, :, 7] = ninf                      # a forbidden tag at one position
+    phi[2, 30, :, :] = ninf                      # no finite path at all
+    mask = torch.rand(N, T, T, generator=torch.Generator().manual_seed(5)) < 0.6
+    phi[3][mask] = ninf                          # sparse transition structure
+    phi[3, :, torch.arange(T), torch.arange(T)] = 0.0
+    lens = torch.tensor([50, 50, 50, 50, 33], dtype=torch.int32)
+    check_case(crf, oracle_mod, phi, lens, poison=False, algo=crf.ALGO_SCAN, what="scan -inf", queries=("logz", "mu"))
+
+
+def test_scan_scale_jumps_take_the_exact_product(crf, oracle_mod, chunk):
+    """Matrices whose entries span hundreds of nats, and scales that jump between positions: the
+    linear-domain chunk product must be rejected and the exact log-domain product used."""
+    chunk(8)
+    T, N = 16, 70
+    phi, lens = workloads.random_case(5400, 4, N, T, scale=1.0, ragged=True, min_len=N // 2)
+    g = torch.Generator().manual_seed(17)
+    jump = (torch.randint(0, 3, (4, N, 1, 1), generator=g).to(torch.float32) - 1.0) * 300.0
+    phi = phi + jump
+    wide = torch.randint(0, 2, (4, N, T, T), generator=g).to(torch.float32) * -150.0
+    wide[:, ::3] = 0.0
+    phi = (phi + wide).contiguous()
+    check_case(crf, oracle_mod, phi, lens, algo=crf.ALGO_SCAN, what="scan jumps", queries=("logz", "mu"))
+
+
+def test_scan_large_offsets(crf, oracle_mod, chunk):
+    chunk(16)
+    phi, lens = workloads.random_case(5500, 3, 120, 16, scale=1.0, ragged=True, min_len=60)
+    phi = (phi + 40.0).contiguous()
+    check_case(crf, oracle_mod, phi, lens, algo=crf.ALGO_SCAN, what="scan offsets", queries=("logz", "mu"))
+
+
+def test_scan_agrees_with_sequential(crf):
+    phi, lens = workloads.random_case(5600, 4, 1000, 16, scale=2.0, ragged=True, min_len=500)
+    dphi, dl = phi.cuda(), lens.cuda()
+    lz_a, mu_a = crf.lccrf_marginals(dphi, dl, algo=crf.ALGO_SCAN)
+    lz_b, mu_b = crf.lccrf_marginals(dphi, dl, algo=crf.ALGO_SEQUENTIAL)
+    lz_c = crf.lccrf_log_partition(dphi, dl, algo=crf.ALGO_SCAN)
+    assert torch.allclose(lz_a, lz_b, rtol=2e-6, atol=0)
+    assert torch.allclose(lz_c, lz_b, rtol=2e-6, atol=0)
+    assert float((mu_a - mu_b).abs().max()) < 5e-6
+
+
+def test_scan_repeat_runs_are_bit_identical(crf):
+    phi, lens = workloads.random_case(5700, 3, 400, 16, scale=2.0, ragged=True, min_len=100)
+    dphi, dl = phi.cuda(), lens.cuda()
+    lz_a, mu_a = crf.lccrf_marginals(dphi, dl, algo=crf.ALGO_SCAN)
+    lz_b, mu_b = crf.lccrf_marginals(dphi, dl, algo=crf.ALGO_SCAN)
+    assert torch.equal(lz_a, lz_b) and torch.equal(mu_a, mu_b)
+
+
+def test_scan_needs_a_small_tag_set(crf):
+    phi, _ = workloads.random_case(5800, 2, 8, 17)
+    with pytest.raises(crf.LccrfError, match="not available"):
+        crf.lccrf_marginals(phi.cuda(), None, algo=crf.ALGO_SCAN)
+    with pytest.raises(crf.LccrfError, match="invalid argument"):
+        crf.set_scan_chunk(3)
+
+
+def test_config5_sequential_schedule(crf, oracle_mod):
+    """Config 5 under the sequential schedule (the default now takes the scan for it)."""
+    w = workloads.WORKLOADS["cfg5"]
+    phi = workloads.phi_batch(w)
+    lens = workloads.lengths(w)
+    check_case(crf, oracle_mod, phi, lens, poison=False, algo=crf.ALGO_SEQUENTIAL, what="cfg5 sequential",
+               queries=("logz", "mu"))
