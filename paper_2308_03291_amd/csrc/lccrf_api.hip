@@ -37,7 +37,22 @@ inline SumWorkspace sum_workspace(size_t B, size_t N, size_t T) {
     w.total = off;
     return w;
 }
-inline size_t max_workspace(size_t B, size_t N, size_t T) { return round_up(B * N * T); }
+struct MaxWorkspace {
+    size_t bp;
+    size_t Mx, K, pin;  // chunked scan (T <= 16 only, else empty)
+    size_t total;
+};
+inline MaxWorkspace max_workspace(size_t B, size_t N, size_t T) {
+    MaxWorkspace w;
+    size_t off = 0;
+    w.bp = off; off += round_up(B * N * T);
+    const size_t BC = lccrf::scan_supported((int)T) ? B * ((N + g_scan_chunk - 1) / g_scan_chunk) : 0;
+    w.Mx = off; off += round_up(BC * 256 * sizeof(double));
+    w.K = off; off += round_up(BC * 16);
+    w.pin = off; off += round_up(BC * sizeof(int32_t));
+    w.total = off;
+    return w;
+}
 
 inline bool shape_ok(int B, int N, int T) {
     if (B < 1 || N < 1 || T < 1 || T > LCCRF_MAX_T) return false;
@@ -119,7 +134,7 @@ size_t lccrf_workspace_bytes(lccrf_op op, int B, int N, int T, lccrf_dtype dt) {
     switch (op) {
         case LCCRF_OP_LOGZ:
         case LCCRF_OP_MARGINALS: return sum_workspace(B, N, T).total;
-        case LCCRF_OP_ARGMAX: return max_workspace(B, N, T);
+        case LCCRF_OP_ARGMAX: return max_workspace(B, N, T).total;
         default: return 0;
     }
 }
@@ -150,10 +165,20 @@ int lccrf_argmax_algo(const void* phi, lccrf_dtype dt, const int32_t* lengths, i
     if (!tags) return LCCRF_ENULL;
     if (!aligned_to(tags, 4) || (best_score && !aligned_to(best_score, 4))) return LCCRF_EALIGN;
     if (lengths && !aligned_to(lengths, 4)) return LCCRF_EALIGN;
-    if (algo == LCCRF_ALGO_SCAN) return LCCRF_ENOTIMPL;
-    const hipError_t e =
-        lccrf::launch_sequential_max(dt, phi, lengths, B, N, T, static_cast<uint8_t*>(workspace), best_score, tags,
-                                     static_cast<hipStream_t>(stream));
+    if (algo == LCCRF_ALGO_SCAN && !lccrf::scan_supported(T)) return LCCRF_ENOTIMPL;
+    const MaxWorkspace w = max_workspace(B, N, T);
+    char* base = static_cast<char*>(workspace);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    uint8_t* bp = reinterpret_cast<uint8_t*>(base + w.bp);
+    hipError_t e;
+    if (algo == LCCRF_ALGO_SCAN || (algo == LCCRF_ALGO_AUTO && scan_pays(B, N, T))) {
+        int32_t* pin = reinterpret_cast<int32_t*>(base + w.pin);
+        e = lccrf::launch_scan_pins(dt, phi, lengths, B, N, T, g_scan_chunk, reinterpret_cast<double*>(base + w.Mx),
+                                    reinterpret_cast<uint8_t*>(base + w.K), pin, best_score, st);
+        if (e == hipSuccess) e = lccrf::launch_chunked_max(dt, phi, lengths, B, N, T, bp, tags, g_scan_chunk, pin, st);
+    } else {
+        e = lccrf::launch_sequential_max(dt, phi, lengths, B, N, T, bp, best_score, tags, st);
+    }
     return e == hipSuccess ? LCCRF_OK : LCCRF_ELAUNCH;
 }
 

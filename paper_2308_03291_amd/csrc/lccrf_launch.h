@@ -45,4 +45,12 @@ hipError_t launch_chunked_marginals(int dtype, const void* phi, const int32_t* l
 hipError_t launch_sequential_max(int dtype, const void* phi, const int32_t* lengths, int B, int N, int T,
                                  uint8_t* bp, float* best_score, int32_t* tags, hipStream_t st);
 
+// Max-plus chunked scan (lccrf_scan.hip): the best score and the tag of the best path at the last
+// position of every chunk (pin: [B][C] ints).  Mx: [B][C][256] doubles, K: [B][C][16] bytes of scratch.
+hipError_t launch_scan_pins(int dtype, const void* phi, const int32_t* lengths, int B, int N, int T, int chunk,
+                            double* Mx, uint8_t* K, int32_t* pin, float* best_score, hipStream_t st);
+// Best path inside every chunk between those pinned tags (lccrf_viterbi.hip).
+hipError_t launch_chunked_max(int dtype, const void* phi, const int32_t* lengths, int B, int N, int T, uint8_t* bp,
+                              int32_t* tags, int chunk, const int32_t* pin, hipStream_t st);
+
 }  // namespace lccrf

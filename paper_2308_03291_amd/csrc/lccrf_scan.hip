@@ -17,8 +17,9 @@
 // Phase A keeps each product in the linear domain, scaled per entry tag by an exact power of
 // two after every position, so that one position costs T^2 exponentials and four
 // v_mfma_f32_16x16x4_f32 instead of T^3 exponentials.  A product is accepted only if no entry
-// that is not structurally zero ever fell below 2^-60 of its scale (then no term that matters
-// was flushed to zero); otherwise the wave recomputes its chunk with the exact log-domain
+// ever fell below 2^-98 of its scale unless no path leads to it at all (the zero pattern is
+// carried along as a product of 0/1 matrices): then no term that matters was flushed to zero.
+// Otherwise the wave recomputes its chunk with the exact log-domain
 // product, every log-sum-exp shifted by its own maximum.  Both forms write the same format:
 // log2 of the scaled product, one integer log2 scale per entry tag and one common offset.
 #include "lccrf_device.h"
@@ -28,7 +29,7 @@ namespace lccrf {
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
-constexpr float kTiny = 0x1p-60f;
+constexpr float kTiny = 0x1p-98f;  // smallest accepted entry of a linear-domain product
 constexpr int kScanPF = 8;
 
 struct ScanArgs {
@@ -92,9 +93,11 @@ __global__ __launch_bounds__(64) void chunk_product_kernel(ScanArgs a) {
             in[v] = s < T && j < T;
             off[v] = (s < T ? s : T - 1) * T + (j < T ? j : T - 1);
         }
-        float D[4];
+        // Z is D's zero pattern (1 where some path exists), carried by a second product of 0/1
+        // matrices: an entry may be zero, or tiny, only where the pattern says no path exists.
+        float D[4], Z[4];
 #pragma unroll
-        for (int v = 0; v < 4; ++v) D[v] = (4 * g + v == j) ? 1.f : 0.f;
+        for (int v = 0; v < 4; ++v) D[v] = Z[v] = (4 * g + v == j) ? 1.f : 0.f;
         float ring[kScanPF][4];
         auto load = [&](int i, int slot) {
             const TIN* m = phib + (size_t)i * TT;
@@ -110,13 +113,14 @@ __global__ __launch_bounds__(64) void chunk_product_kernel(ScanArgs a) {
             for (int v = 0; v < 4; ++v) x[v] = in[v] ? ring[slot][v] * kLog2e : LCCRF_NEG_INF;
             const float m = finite_or_zero(xor_max<1, 64>(fmaxf(fmaxf(x[0], x[1]), fmaxf(x[2], x[3]))));
             Msum += (double)m;
-            f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+            f32x4 acc = {0.f, 0.f, 0.f, 0.f}, pat = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
             for (int v = 0; v < 4; ++v) {
-                const float E = ex2(x[v] - m);
-                bad |= (E < kTiny) & (x[v] > LCCRF_NEG_INF);
-                acc = __builtin_amdgcn_mfma_f32_16x16x4f32(E, D[v], acc, 0, 0, 0);
+                acc = __builtin_amdgcn_mfma_f32_16x16x4f32(ex2(x[v] - m), D[v], acc, 0, 0, 0);
+                pat = __builtin_amdgcn_mfma_f32_16x16x4f32(x[v] > LCCRF_NEG_INF ? 1.f : 0.f, Z[v], pat, 0, 0, 0);
             }
+            // With the column maxima of D in [1, 2) and those of E at most 1, a term lost to
+            // underflow is below 2^-126: it cannot matter to a sum that is at least kTiny.
             // power-of-two rescale of each entry tag's column (exact)
             const float cm = xor_max<16, 64>(fmaxf(fmaxf(acc[0], acc[1]), fmaxf(acc[2], acc[3])));
             const int ex = cm > 0.f ? ((__float_as_int(cm) >> 23) & 0xff) - 127 : 0;
@@ -124,8 +128,9 @@ __global__ __launch_bounds__(64) void chunk_product_kernel(ScanArgs a) {
             esum += ex;
 #pragma unroll
             for (int v = 0; v < 4; ++v) {
+                Z[v] = pat[v] > 0.f ? 1.f : 0.f;
+                bad |= (pat[v] > 0.f) & !(acc[v] >= kTiny);
                 D[v] = acc[v] * sc;
-                bad |= (D[v] != 0.f) & !(D[v] >= kTiny);
             }
         });
         if (__builtin_amdgcn_ballot_w64(bad) == 0) {
@@ -284,6 +289,171 @@ __global__ __launch_bounds__(64) void chunk_boundary_kernel(ScanArgs a) {
     }
 }
 
+
+// ---------------------------------------------------------------------------------------
+// Max-plus analogue (section "Computing Most Probable Structure": the same recursion with max in
+// place of log-sum-exp).  Scores stay unscaled in double precision like the sequential Viterbi
+// kernel's, so the scan compares the same sums up to the rounding of their last bit.
+//
+//   phase A: M_c[r][s] = best score of a path through chunk c from tag r (one position before
+//       the chunk) to tag s (its last position);
+//   phase B: delta at the last position of every chunk with the best entry tag per exit tag,
+//       then the back-trace over chunks: the tag at the last position of every chunk (pin);
+//   phase C (viterbi_kernel of lccrf_viterbi.hip, one workgroup per chunk): the best path
+//       inside every chunk between its two pinned tags, so the stitched path is one valid path.
+struct MaxScanArgs {
+    const void* phi;
+    const int32_t* lengths;
+    int B, N, T;
+    int chunk, C;
+    double* Mx;     // [B][C][16][16]  M_c[r][s], -inf padded
+    uint8_t* K;     // [B][C][16]      best entry tag for each exit tag
+    int32_t* pin;   // [B][C]
+    float* best_score;
+};
+
+template <typename TIN>
+__global__ __launch_bounds__(64) void chunk_maxplus_kernel(MaxScanArgs a) {
+    __shared__ __attribute__((aligned(16))) double Mc[16][18];
+    __shared__ __attribute__((aligned(16))) float Ph[16][16];
+    const int lane = threadIdx.x, r = lane >> 2, q = lane & 3;
+    const int b = blockIdx.x / a.C, c = blockIdx.x % a.C;
+    const int T = a.T, N = a.N;
+    const int L = clamp_length(a.lengths, b, N);
+    if (c * a.chunk >= L) return;
+    int first, last;
+    chunk_range(c, a.chunk, L, first, last);
+    const size_t TT = (size_t)T * T;
+    const TIN* phib = static_cast<const TIN*>(a.phi) + (size_t)b * N * TT;
+    const double ninf = -__builtin_huge_val();
+    // this lane stages phi_i[r][4q .. 4q+3] and owns M[r][4q .. 4q+3]
+    int off[4];
+    bool in[4];
+#pragma unroll
+    for (int jj = 0; jj < 4; ++jj) {
+        const int t = 4 * q + jj;
+        in[jj] = r < T && t < T;
+        off[jj] = (r < T ? r : T - 1) * T + (t < T ? t : T - 1);
+    }
+    double M[4];
+#pragma unroll
+    for (int jj = 0; jj < 4; ++jj) M[jj] = (r == 4 * q + jj) ? 0.0 : ninf;
+    float ring[kScanPF][4];
+    auto load = [&](int i, int slot) {
+        const TIN* m = phib + (size_t)i * TT;
+#pragma unroll
+        for (int jj = 0; jj < 4; ++jj) ring[slot][jj] = Elem<TIN>::get(m + off[jj]);
+    };
+    walk<kScanPF>(first, last, +1, load, [&](int, int slot) {
+        __syncthreads();
+#pragma unroll
+        for (int jj = 0; jj < 4; ++jj) {
+            Ph[r][4 * q + jj] = in[jj] ? ring[slot][jj] : LCCRF_NEG_INF;
+            Mc[r][4 * q + jj] = M[jj];
+        }
+        __syncthreads();
+        double best[4] = {ninf, ninf, ninf, ninf};
+#pragma unroll
+        for (int s = 0; s < 16; ++s) {
+            const double m = Mc[r][s];
+            const float4 f = *reinterpret_cast<const float4*>(&Ph[s][4 * q]);
+            best[0] = fmax(best[0], m + (double)f.x);
+            best[1] = fmax(best[1], m + (double)f.y);
+            best[2] = fmax(best[2], m + (double)f.z);
+            best[3] = fmax(best[3], m + (double)f.w);
+        }
+#pragma unroll
+        for (int jj = 0; jj < 4; ++jj) M[jj] = best[jj];
+    });
+    double* out = a.Mx + ((size_t)b * a.C + c) * 256 + r * 16 + 4 * q;
+#pragma unroll
+    for (int jj = 0; jj < 4; ++jj) out[jj] = (r < T && 4 * q + jj < T) ? M[jj] : ninf;
+}
+
+constexpr int kPinWindow = 1024;  // chunks of back-pointers held in LDS at a time by the back-trace
+
+template <typename TIN>
+__global__ __launch_bounds__(64) void chunk_maxplus_boundary_kernel(MaxScanArgs a) {
+    __shared__ __attribute__((aligned(16))) double vec[2][16];
+    __shared__ uint8_t win[kPinWindow * 16];
+    const int lane = threadIdx.x, t = lane >> 2, q = lane & 3;
+    const int b = blockIdx.x;
+    const int T = a.T, N = a.N;
+    const int L = clamp_length(a.lengths, b, N);
+    if (L == 0) {
+        if (lane == 0 && a.best_score) a.best_score[b] = 0.f;
+        return;
+    }
+    const int Cb = (L + a.chunk - 1) / a.chunk;
+    const size_t cb = (size_t)b * a.C;
+    const double ninf = -__builtin_huge_val();
+    const TIN* phib = static_cast<const TIN*>(a.phi) + (size_t)b * N * T * T;
+    if (lane < 16) vec[0][lane] = (lane < T) ? (double)Elem<TIN>::get(phib + lane) : ninf;  // delta_0
+    __syncthreads();
+    int buf = 0;
+    double mm[kScanPF][4];
+    auto load = [&](int c, int slot) {
+        const double* M = a.Mx + (cb + c) * 256;
+#pragma unroll
+        for (int jj = 0; jj < 4; ++jj) mm[slot][jj] = M[(4 * q + jj) * 16 + t];
+    };
+    double dv = ninf;
+    walk<kScanPF>(0, Cb - 1, +1, load, [&](int c, int slot) {
+        double bv = ninf;
+        int ba = 0x7fffffff;
+#pragma unroll
+        for (int jj = 0; jj < 4; ++jj) {  // ascending entry tags: the first maximum wins
+            const double val = vec[buf][4 * q + jj] + mm[slot][jj];
+            if (val > bv) { bv = val; ba = 4 * q + jj; }
+        }
+#pragma unroll
+        for (int off = 1; off < 4; off <<= 1) {
+            const double pv = __shfl_xor(bv, off, 64);
+            const int pa = __shfl_xor(ba, off, 64);
+            if (pv > bv || (pv == bv && pa < ba)) { bv = pv; ba = pa; }
+        }
+        dv = bv;
+        buf ^= 1;
+        if (q == 0) {
+            vec[buf][t] = bv;
+            a.K[(cb + c) * 16 + t] = (uint8_t)(ba == 0x7fffffff ? 0 : ba);
+        }
+        __syncthreads();
+    });
+    // best tag at the last position: first maximum (entry t sits in lanes 4t .. 4t+3)
+    double bv = (q == 0 && t < T) ? dv : ninf;
+    int ba = (q == 0 && t < T) ? t : 0x7fffffff;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        const double pv = __shfl_xor(bv, off, 64);
+        const int pa = __shfl_xor(ba, off, 64);
+        if (pv > bv || (pv == bv && pa < ba)) { bv = pv; ba = pa; }
+    }
+    if (ba == 0x7fffffff) ba = 0;
+    if (lane == 0 && a.best_score) a.best_score[b] = (float)bv;
+    __threadfence();  // K written above is read back below by other lanes
+    __syncthreads();
+    // back-trace over chunks through an LDS window of K
+    int y = ba;
+    int hi = Cb;  // chunks [1, hi) still to walk: chunk c maps the tag at its end to the tag at the end of c - 1
+    if (lane == 0) a.pin[cb + Cb - 1] = y;
+    while (hi > 1) {
+        const int lo = (hi - kPinWindow > 1) ? hi - kPinWindow : 1;
+        const int nbytes = (hi - lo) * 16;
+        const uint8_t* src = a.K + (cb + lo) * 16;
+        for (int k = lane; k < nbytes; k += 64) win[k] = src[k];
+        __syncthreads();
+        if (lane == 0) {
+            for (int c = hi - 1; c >= lo; --c) {
+                y = win[(c - lo) * 16 + y];
+                a.pin[cb + c - 1] = y;
+            }
+        }
+        __syncthreads();
+        hi = lo;
+    }
+}
+
 // ---------------------------------------------------------------------------------------
 bool scan_supported(int T) { return T >= 1 && T <= 16; }
 
@@ -302,6 +472,24 @@ hipError_t launch_scan_boundaries(int dtype, const void* phi, const int32_t* len
         hipLaunchKernelGGL(chunk_boundary_kernel<float>, dim3(2 * B), dim3(64), 0, st, a);
     else
         hipLaunchKernelGGL(chunk_boundary_kernel<uint16_t>, dim3(2 * B), dim3(64), 0, st, a);
+    return hipGetLastError();
+}
+
+
+hipError_t launch_scan_pins(int dtype, const void* phi, const int32_t* lengths, int B, int N, int T, int chunk,
+                            double* Mx, uint8_t* K, int32_t* pin, float* best_score, hipStream_t st) {
+    const int C = (N + chunk - 1) / chunk;
+    MaxScanArgs a{phi, lengths, B, N, T, chunk, C, Mx, K, pin, best_score};
+    if (dtype == 0)
+        hipLaunchKernelGGL(chunk_maxplus_kernel<float>, dim3(B * C), dim3(64), 0, st, a);
+    else
+        hipLaunchKernelGGL(chunk_maxplus_kernel<uint16_t>, dim3(B * C), dim3(64), 0, st, a);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    if (dtype == 0)
+        hipLaunchKernelGGL(chunk_maxplus_boundary_kernel<float>, dim3(B), dim3(64), 0, st, a);
+    else
+        hipLaunchKernelGGL(chunk_maxplus_boundary_kernel<uint16_t>, dim3(B), dim3(64), 0, st, a);
     return hipGetLastError();
 }
 

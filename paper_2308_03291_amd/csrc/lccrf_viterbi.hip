@@ -39,6 +39,12 @@ struct VitArgs {
     uint8_t* bp;  // [B][N][T]
     float* best_score;
     int32_t* tags;
+    // Chunked schedule (chunk > 0): workgroup v serves chunk c = v % C of sequence v / C, the tag
+    // positions [c chunk, (c+1) chunk), as a chain of its own that starts one position earlier in
+    // the tag pin[b][c-1] and must end in the tag pin[b][c] (both chosen by the max-plus scan,
+    // lccrf_scan.hip); the best score is the scan's and is not written here.
+    int chunk, C;
+    const int32_t* pin;  // [B][C] tag at the last position of each chunk
 };
 
 template <typename G, typename TIN, bool ALIGNED>
@@ -46,15 +52,24 @@ __global__ __launch_bounds__(G::W) void viterbi_kernel(VitArgs a) {
     __shared__ VitSmem<G> sm;
     constexpr int ITEMS = G::ITEMS;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int b = blockIdx.x;
+    const bool chunked = a.chunk > 0;
+    const int b = chunked ? blockIdx.x / a.C : blockIdx.x;
+    const int c = chunked ? blockIdx.x % a.C : 0;
     const int N = a.N, T = a.T;
     const int L = clamp_length(a.lengths, b, N);
     int32_t* tags = a.tags + (size_t)b * N;
-    for (int i = L + tid; i < N; i += G::W) tags[i] = -1;
+    // this workgroup's stretch of tag positions [t0, t1), cut at the length: first position p0
+    // (carries the start vector) and last position e of its chain
+    const int t0 = chunked ? c * a.chunk : 0;
+    const int t1 = chunked ? (t0 + a.chunk < N ? t0 + a.chunk : N) : N;
+    for (int i = (L > t0 ? L : t0) + tid; i < t1; i += G::W) tags[i] = -1;
     if (L == 0) {
-        if (tid == 0 && a.best_score) a.best_score[b] = 0.f;
+        if (!chunked && tid == 0 && a.best_score) a.best_score[b] = 0.f;
         return;
     }
+    if (t0 >= L) return;
+    const int p0 = t0 > 0 ? t0 - 1 : 0;
+    const int e = (t1 < L ? t1 : L) - 1;
     const int c4 = 4 * (tid % G::LPR), r0 = tid / G::LPR;
     const size_t TT = (size_t)T * T;
     const TIN* phib = static_cast<const TIN*>(a.phi) + (size_t)b * N * TT;
@@ -63,7 +78,10 @@ __global__ __launch_bounds__(G::W) void viterbi_kernel(VitArgs a) {
 
     for (int k = tid; k < 2 * G::TCAP; k += G::W) (&sm.dvec[0][0])[k] = ninf;
     __syncthreads();
-    if (tid < T) sm.dvec[0][tid] = (double)Elem<TIN>::get(phib + tid);
+    if (tid < T) {
+        if (t0 == 0) sm.dvec[0][tid] = (double)Elem<TIN>::get(phib + tid);
+        else sm.dvec[0][tid] = (tid == a.pin[(size_t)b * a.C + c - 1]) ? 0.0 : ninf;
+    }
     __syncthreads();
 
     int buf = 0;
@@ -110,19 +128,21 @@ __global__ __launch_bounds__(G::W) void viterbi_kernel(VitArgs a) {
         __syncthreads();
         buf ^= 1;
     };
-    int i = 1;
-    if (i < L) load_tile<G, TIN, ALIGNED>(phib + (size_t)i * TT, T, c4, r0, A);
-    while (i < L) {
-        if (i + 1 < L) load_tile<G, TIN, ALIGNED>(phib + (size_t)(i + 1) * TT, T, c4, r0, Bq);
+    int i = p0 + 1;
+    if (i <= e) load_tile<G, TIN, ALIGNED>(phib + (size_t)i * TT, T, c4, r0, A);
+    while (i <= e) {
+        if (i + 1 <= e) load_tile<G, TIN, ALIGNED>(phib + (size_t)(i + 1) * TT, T, c4, r0, Bq);
         step(i, A);
-        if (++i >= L) break;
-        if (i + 1 < L) load_tile<G, TIN, ALIGNED>(phib + (size_t)(i + 1) * TT, T, c4, r0, A);
+        if (++i > e) break;
+        if (i + 1 <= e) load_tile<G, TIN, ALIGNED>(phib + (size_t)(i + 1) * TT, T, c4, r0, A);
         step(i, Bq);
         ++i;
     }
 
-    // best final tag: first maximum of delta_{L-1}
-    if (wave == 0) {
+    if (chunked) {
+        if (tid == 0) sm.last = a.pin[(size_t)b * a.C + c];
+    } else if (wave == 0) {
+        // best final tag: first maximum of delta_{L-1}
         double bv = ninf;
         int ba = kNoArg;
         for (int t = lane; t < T; t += 64) {
@@ -145,12 +165,14 @@ __global__ __launch_bounds__(G::W) void viterbi_kernel(VitArgs a) {
     __syncthreads();
 
     // back-trace: y_{i-1} = bp_i(y_i), walked through an LDS window of back-pointers
+    // (a chunk leaves the tag of its entry position p0 to the chunk that ends there)
     const int rows_per_window = kTraceBytes / T;
     int y = sm.last;
-    if (tid == 0) tags[L - 1] = y;
-    int hi = L;  // rows [1, hi) still to walk
-    while (hi > 1) {
-        const int lo = (hi - rows_per_window > 1) ? hi - rows_per_window : 1;
+    if (tid == 0) tags[e] = y;
+    const int stop = t0 == 0 ? 1 : t0 + 1;  // rows [stop, hi) still to walk; row r yields tag r - 1
+    int hi = e + 1;
+    while (hi > stop) {
+        const int lo = (hi - rows_per_window > stop) ? hi - rows_per_window : stop;
         const int nbytes = (hi - lo) * T;
         const uint8_t* src = bpb + (size_t)lo * T;
         for (int k = tid; k < nbytes; k += G::W) sm.u.window[k] = src[k];
@@ -168,7 +190,7 @@ __global__ __launch_bounds__(G::W) void viterbi_kernel(VitArgs a) {
 
 template <typename G, typename TIN, bool ALIGNED>
 static hipError_t launch_geo(const VitArgs& a, hipStream_t st) {
-    hipLaunchKernelGGL((viterbi_kernel<G, TIN, ALIGNED>), dim3(a.B), dim3(G::W), 0, st, a);
+    hipLaunchKernelGGL((viterbi_kernel<G, TIN, ALIGNED>), dim3(a.B * a.C), dim3(G::W), 0, st, a);
     return hipGetLastError();
 }
 
@@ -186,7 +208,16 @@ static hipError_t launch_T(const VitArgs& a, hipStream_t st) {
 
 hipError_t launch_sequential_max(int dtype, const void* phi, const int32_t* lengths, int B, int N, int T,
                                  uint8_t* bp, float* best_score, int32_t* tags, hipStream_t st) {
-    VitArgs a{phi, lengths, B, N, T, bp, best_score, tags};
+    VitArgs a{phi, lengths, B, N, T, bp, best_score, tags, 0, 1, nullptr};
+    const bool aligned = (T % 4) == 0;
+    if (dtype == 0) return aligned ? launch_T<float, true>(a, st) : launch_T<float, false>(a, st);
+    return aligned ? launch_T<uint16_t, true>(a, st) : launch_T<uint16_t, false>(a, st);
+}
+
+// Best path inside every chunk between the tags the max-plus scan has pinned at the chunk ends.
+hipError_t launch_chunked_max(int dtype, const void* phi, const int32_t* lengths, int B, int N, int T, uint8_t* bp,
+                              int32_t* tags, int chunk, const int32_t* pin, hipStream_t st) {
+    VitArgs a{phi, lengths, B, N, T, bp, nullptr, tags, chunk, (N + chunk - 1) / chunk, pin};
     const bool aligned = (T % 4) == 0;
     if (dtype == 0) return aligned ? launch_T<float, true>(a, st) : launch_T<float, false>(a, st);
     return aligned ? launch_T<uint16_t, true>(a, st) : launch_T<uint16_t, false>(a, st);
