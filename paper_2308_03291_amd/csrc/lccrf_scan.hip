@@ -14,11 +14,11 @@
 //   phase C (the chain kernels of lccrf_chain.hip, one pair of workgroups per chunk):
 //       the ordinary two-chain forward-backward inside every chunk, started from F and G.
 //
-// Phase A keeps each product in the linear domain, scaled per entry tag by an exact power of
-// two after every position, so that one position costs T^2 exponentials and four
-// v_mfma_f32_16x16x4_f32 instead of T^3 exponentials.  A product is accepted only if no entry
-// ever fell below 2^-98 of its scale unless no path leads to it at all (the zero pattern is
-// carried along as a product of 0/1 matrices): then no term that matters was flushed to zero.
+// Phase A keeps each product in the linear domain, in double precision, scaled per entry tag by
+// an exact power of two after every position, so that one position costs T^2 exponentials and
+// four v_mfma_f64_16x16x4_f64 instead of T^3 exponentials.  A product is accepted only if no
+// entry ever fell below 2^-900 of its scale unless no path leads to it at all (the zero pattern
+// is carried along as a product of 0/1 matrices): then no term that matters was flushed to zero.
 // Otherwise the wave recomputes its chunk with the exact log-domain
 // product, every log-sum-exp shifted by its own maximum.  Both forms write the same format:
 // log2 of the scaled product, one integer log2 scale per entry tag and one common offset.
@@ -28,8 +28,9 @@
 namespace lccrf {
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef double f64x4 __attribute__((ext_vector_type(4)));
 
-constexpr float kTiny = 0x1p-98f;  // smallest accepted entry of a linear-domain product
+constexpr double kTiny = 0x1p-900;  // smallest accepted entry of a linear-domain product
 constexpr int kScanPF = 8;
 
 struct ScanArgs {
@@ -76,12 +77,12 @@ __global__ __launch_bounds__(64) void chunk_product_kernel(ScanArgs a) {
     float* rel_out = a.rel + ((size_t)b * a.C + c) * 16;
     double* base_out = a.base + (size_t)b * a.C + c;
 
-    // ---- linear-domain product on the matrix cores.
-    // D[s][r] (exit tag s, entry tag r) sits in the accumulator layout of the 16x16x4 MFMA:
-    // lane (g = lane / 16, j = lane % 16) holds D[4g + v][j], v = 0..3.  The same lane loads
-    // phi_i[4g + v][j]; as the A operand of MFMA number v that is E^T[j][k = g] for the inner
-    // index s = 4g + v, and D's own register v is the matching B operand, so
-    //     D_new[t][r] = sum_v sum_g E[4g + v][t] D[4g + v][r] = sum_s E[s][t] D[s][r]
+    // ---- linear-domain product on the matrix cores, in double precision for its exponent range.
+    // D[s][r] (exit tag s, entry tag r) sits in the accumulator layout of the 16x16x4 f64 MFMA:
+    // lane (g = lane / 16, j = lane % 16) holds D[g + 4v][j], v = 0..3.  The same lane loads
+    // phi_i[g + 4v][j]; as the A operand of MFMA number v that is E^T[j][k = g] for the inner
+    // index s = g + 4v, and D's own register v is the matching B operand, so
+    //     D_new[t][r] = sum_v sum_g E[g + 4v][t] D[g + 4v][r] = sum_s E[s][t] D[s][r]
     // needs no data movement between positions.
     {
         const int g = lane >> 4, j = lane & 15;
@@ -89,15 +90,22 @@ __global__ __launch_bounds__(64) void chunk_product_kernel(ScanArgs a) {
         bool in[4];
 #pragma unroll
         for (int v = 0; v < 4; ++v) {
-            const int s = 4 * g + v;
+            const int s = g + 4 * v;
             in[v] = s < T && j < T;
             off[v] = (s < T ? s : T - 1) * T + (j < T ? j : T - 1);
         }
-        // Z is D's zero pattern (1 where some path exists), carried by a second product of 0/1
-        // matrices: an entry may be zero, or tiny, only where the pattern says no path exists.
-        float D[4], Z[4];
+        // The zero pattern of D (1 where some path exists) is carried along by a product of 0/1
+        // matrices on the f32 MFMA, from the first matrix with a -inf entry on (until then D is
+        // the identity or has no zero).  That instruction numbers its output rows 4g + v, so it
+        // runs on rows renamed by pi(4g + v) = g + 4v: its A operand is the flag of column pi(j).
+        const int pj = (lane & 48) | (4 * (j & 3) + (j >> 2));
+        double D[4];
+        float Z[4];
 #pragma unroll
-        for (int v = 0; v < 4; ++v) D[v] = Z[v] = (4 * g + v == j) ? 1.f : 0.f;
+        for (int v = 0; v < 4; ++v) {
+            D[v] = (g + 4 * v == j) ? 1.0 : 0.0;
+            Z[v] = (g + 4 * v == j) ? 1.f : 0.f;
+        }
         float ring[kScanPF][4];
         auto load = [&](int i, int slot) {
             const TIN* m = phib + (size_t)i * TT;
@@ -106,38 +114,74 @@ __global__ __launch_bounds__(64) void chunk_product_kernel(ScanArgs a) {
         };
         double Msum = 0.0;
         int esum = 0;
-        bool bad = false;
+        bool bad = false, tracking = false, started = false;
         walk<kScanPF>(first, last, +1, load, [&](int, int slot) {
             float x[4];
 #pragma unroll
             for (int v = 0; v < 4; ++v) x[v] = in[v] ? ring[slot][v] * kLog2e : LCCRF_NEG_INF;
             const float m = finite_or_zero(xor_max<1, 64>(fmaxf(fmaxf(x[0], x[1]), fmaxf(x[2], x[3]))));
             Msum += (double)m;
-            f32x4 acc = {0.f, 0.f, 0.f, 0.f}, pat = {0.f, 0.f, 0.f, 0.f};
+            int nz = 0;
+            f64x4 acc = {0.0, 0.0, 0.0, 0.0};
 #pragma unroll
             for (int v = 0; v < 4; ++v) {
-                acc = __builtin_amdgcn_mfma_f32_16x16x4f32(ex2(x[v] - m), D[v], acc, 0, 0, 0);
-                pat = __builtin_amdgcn_mfma_f32_16x16x4f32(x[v] > LCCRF_NEG_INF ? 1.f : 0.f, Z[v], pat, 0, 0, 0);
+                // E = 2^(x - m) in double: the fraction through the float exponential, the integer
+                // part through the exponent field
+                const float d = x[v] - m, di = floorf(d);
+                const double E = d > -1000.f ? ldexp((double)ex2(d - di), (int)di) : 0.0;
+                nz |= (x[v] > LCCRF_NEG_INF) ? (1 << v) : 0;
+                acc = __builtin_amdgcn_mfma_f64_16x16x4f64(E, D[v], acc, 0, 0, 0);
             }
-            // With the column maxima of D in [1, 2) and those of E at most 1, a term lost to
-            // underflow is below 2^-126: it cannot matter to a sum that is at least kTiny.
-            // power-of-two rescale of each entry tag's column (exact)
-            const float cm = xor_max<16, 64>(fmaxf(fmaxf(acc[0], acc[1]), fmaxf(acc[2], acc[3])));
-            const int ex = cm > 0.f ? ((__float_as_int(cm) >> 23) & 0xff) - 127 : 0;
-            const float sc = __int_as_float((127 - ex) << 23);
+            const bool hole = (in[0] && !(nz & 1)) || (in[1] && !(nz & 2)) || (in[2] && !(nz & 4)) || (in[3] && !(nz & 8));
+            if (!tracking && __builtin_amdgcn_ballot_w64(hole) != 0) {
+                tracking = true;
+                if (started) {
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) Z[v] = in[v] ? 1.f : 0.f;
+                }
+            }
+            started = true;
+            if (tracking) {
+                const int nzp = __shfl(nz, pj, 64);
+                f32x4 pat = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int v = 0; v < 4; ++v)
+                    pat = __builtin_amdgcn_mfma_f32_16x16x4f32((nzp >> v) & 1 ? 1.f : 0.f, Z[v], pat, 0, 0, 0);
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    Z[v] = pat[v] > 0.f ? 1.f : 0.f;
+                    bad |= (pat[v] > 0.f) & !(acc[v] >= kTiny);
+                }
+            } else {
+#pragma unroll
+                for (int v = 0; v < 4; ++v) bad |= in[v] & !(acc[v] >= kTiny);
+            }
+            // With the column maxima of D in [1, 2) and E at most 1, a term lost to underflow is
+            // below 2^-1022: it cannot matter to a sum that is at least kTiny.
+            // Power-of-two rescale of each entry tag's column (exact): the largest exponent field.
+            int ef = 0;
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const int f = (__double2hiint(acc[v]) >> 20) & 0x7ff;
+                ef = f > ef ? f : ef;
+            }
+            {
+                const auto r16 = __builtin_amdgcn_permlane16_swap(ef, ef, false, false);
+                ef = (int)r16[0] > (int)r16[1] ? (int)r16[0] : (int)r16[1];
+                const auto r32 = __builtin_amdgcn_permlane32_swap(ef, ef, false, false);
+                ef = (int)r32[0] > (int)r32[1] ? (int)r32[0] : (int)r32[1];
+            }
+            const int ex = ef > 0 ? ef - 1023 : 0;
             esum += ex;
 #pragma unroll
-            for (int v = 0; v < 4; ++v) {
-                Z[v] = pat[v] > 0.f ? 1.f : 0.f;
-                bad |= (pat[v] > 0.f) & !(acc[v] >= kTiny);
-                D[v] = acc[v] * sc;
-            }
+            for (int v = 0; v < 4; ++v) D[v] = ldexp(acc[v], -ex);
         });
         if (__builtin_amdgcn_ballot_w64(bad) == 0) {
             const float ef = j < T ? (float)esum : LCCRF_NEG_INF;
             const float emax = finite_or_zero(xor_max<1, 16>(ef));
 #pragma unroll
-            for (int v = 0; v < 4; ++v) Pout[(4 * g + v) * 16 + j] = (in[v] && D[v] > 0.f) ? lg2(D[v]) : LCCRF_NEG_INF;
+            for (int v = 0; v < 4; ++v)
+                Pout[(g + 4 * v) * 16 + j] = (in[v] && D[v] > 0.0) ? (float)log2(D[v]) : LCCRF_NEG_INF;
             if (g == 0) rel_out[j] = ef - emax;
             if (lane == 0) *base_out = Msum + (double)emax;
             return;
