@@ -34,6 +34,7 @@
 // a position must sum to one; the sum actually written at one step is fed back as a
 // correction (kappa) to the next, so rounding drift between the forward and the backward
 // offsets (a random walk over thousands of float32 steps) never builds up in the output.
+#include "lccrf_chain_args.h"
 #include "lccrf_device.h"
 #include "lccrf_launch.h"
 
@@ -58,8 +59,6 @@ __device__ __forceinline__ void smem_init(ChainSmem<G>& sm, int tid) {
     if (tid < 4) sm.bad[tid] = 0;
 }
 
-constexpr float kSumLo = 0x1p-60f, kSumHi = 0x1p60f;  // accepted range of a speculative sum
-__device__ __forceinline__ bool sum_in_range(float S) { return S >= kSumLo && S <= kSumHi; }  // false for NaN
 
 // Normaliser of the vector in rvec[buf]: its maximum (0 if the vector is all -inf).
 template <typename G>
@@ -94,23 +93,6 @@ __device__ __forceinline__ void publish_columns(ChainSmem<G>& sm, int nbuf, int 
         if (tid < G::TCAP) sm.rvec[nbuf][tid] = r;
         const float wm = xor_max<1, 64>(r);
         if ((tid & 63) == 0) sm.wmax[nbuf][tid >> 6] = wm;
-    }
-}
-
-// Store 4 consecutive marginals of row s (columns c4 .. c4+3), only those inside the matrix.
-template <bool ALIGNED>
-__device__ __forceinline__ void store4(float* __restrict__ mu_out, int T, int s, int c4,
-                                       float a0, float a1, float a2, float a3) {
-    if (s < T && c4 < T) {
-        float* p = mu_out + (size_t)s * T + c4;
-        if (ALIGNED) {
-            *reinterpret_cast<float4*>(p) = make_float4(a0, a1, a2, a3);
-        } else {
-            p[0] = a0;
-            if (c4 + 1 < T) p[1] = a1;
-            if (c4 + 2 < T) p[2] = a2;
-            if (c4 + 3 < T) p[3] = a3;
-        }
     }
 }
 
@@ -339,58 +321,6 @@ __device__ __forceinline__ void bwd_exact(ChainSmem<G>& sm, int buf, int tid, in
         if (lane == 0) sm.wtot[buf ^ 1][wave] = tot;
     }
     __syncthreads();
-}
-
-struct ChainArgs {
-    const void* phi;
-    const int32_t* lengths;
-    int B, N, T;
-    float* ua;   // [B][N][T] normalised forward vectors (base-2 logs)
-    float* ub;   // [B][N][T] normalised backward vectors
-    double* Oa;  // [B][N] forward offsets:  alpha_i = (ua_i + Oa_i) * ln 2
-    double* Ob;  // [B][N] backward offsets
-    float* logZ;
-    float* mu;
-    int exact_only;  // 1: never take the speculative step (tests)
-    const int* only_failed;  // second pass: if set, recompute only the sequences flagged here
-    // Chunked schedule (chunk > 0): workgroup pair v serves chunk c = v % C of sequence v / C, the
-    // tag positions [c chunk, (c+1) chunk), as a chain of its own that starts one position earlier
-    // from the boundary vectors the scan has produced (lccrf_scan.hip).
-    int chunk, C;
-    const float* Fv;   // [B][C][T] alpha at the last position of each chunk, normalised
-    const double* OF;  // [B][C] its offset
-    const float* Gv;   // [B][C][T] beta at the last position of each chunk, normalised
-    const double* OG;  // [B][C]
-};
-
-// The stretch of positions one pair of workgroups handles: all of a sequence, or one chunk.
-struct Span {
-    int b, c;
-    int L;       // clamped length of the sequence
-    int p0, e;   // first and last position of the chain (p0 carries the start vector)
-    bool first;  // p0 is position 0: start from the first row of the first matrix
-    bool last;   // e is the last position of the sequence: beta = 0 there
-    bool empty;  // nothing to do
-};
-
-__device__ __forceinline__ Span make_span(const ChainArgs& a, int v) {
-    Span s;
-    if (a.chunk <= 0) {
-        s.b = v; s.c = 0;
-        s.L = clamp_length(a.lengths, s.b, a.N);
-        s.p0 = 0; s.e = s.L - 1; s.first = true; s.last = true; s.empty = s.L == 0;
-    } else {
-        s.b = v / a.C; s.c = v % a.C;
-        s.L = clamp_length(a.lengths, s.b, a.N);
-        const int t0 = s.c * a.chunk;
-        s.empty = t0 >= s.L;
-        s.first = s.c == 0;
-        s.p0 = s.first ? 0 : t0 - 1;
-        const int t1 = t0 + a.chunk;
-        s.e = (t1 < s.L ? t1 : s.L) - 1;
-        s.last = s.e == s.L - 1;
-    }
-    return s;
 }
 
 // One position of a forward chain: speculative step, exact replay if it was rejected.
@@ -710,14 +640,25 @@ static hipError_t launch_geo(int op, ChainArgs a, hipStream_t st, hipEvent_t bet
 
 template <typename TIN, bool ALIGNED>
 static hipError_t launch_T(int op, const ChainArgs& a, hipStream_t st, hipEvent_t between, const PairPlan& pair) {
-    const int T = a.T;
-    if (T <= 4) return launch_geo<Geo<1, 1, 1>, TIN, ALIGNED, 4, 4>(op, a, st, between, pair);
-    if (T <= 8) return launch_geo<Geo<2, 1, 1>, TIN, ALIGNED, 4, 4>(op, a, st, between, pair);
-    if (T <= 16) return launch_geo<Geo<4, 1, 1>, TIN, ALIGNED, 4, 4>(op, a, st, between, pair);
-    if (T <= 32) return launch_geo<Geo<8, 4, 1>, TIN, ALIGNED, 4, 4>(op, a, st, between, pair);
+    const int T = a.T;  // T <= 32 is served by the one-wave kernels (launch_wave)
     if (T <= 64) return launch_geo<Geo<16, 4, 4>, TIN, ALIGNED, 4, 3>(op, a, st, between, pair);
     if (T <= 128) return launch_geo<Geo<32, 16, 4>, TIN, ALIGNED, 4, 3>(op, a, st, between, pair);
     return launch_geo<Geo<64, 16, 16>, TIN, ALIGNED, 1, 1>(op, a, st, between, pair);
+}
+
+// Both passes with one wave per chain (T <= 32).
+static hipError_t launch_wave(int op, int dtype, const ChainArgs& a, hipStream_t st, hipEvent_t between) {
+    hipError_t e = launch_wave_pass(false, dtype, a, st);
+    if (e != hipSuccess) return e;
+    if (between) {
+        e = hipEventRecord(between, st);
+        if (e != hipSuccess) return e;
+    }
+    if (op == 0) {
+        hipLaunchKernelGGL(logz_combine_kernel, dim3(a.B), dim3(64), 0, st, a);
+        return hipGetLastError();
+    }
+    return launch_wave_pass(true, dtype, a, st);
 }
 
 // op: 0 = logZ only, 1 = marginals (+ logZ).  Workspace pointers already carved by the caller.
@@ -726,6 +667,7 @@ hipError_t launch_sequential_sum(int op, int dtype, const void* phi, const int32
                                  hipStream_t st, hipEvent_t between, bool exact_only, unsigned long long* mail,
                                  int* failed) {
     ChainArgs a{phi, lengths, B, N, T, ua, ub, Oa, Ob, logZ, mu, exact_only ? 1 : 0, nullptr, 0, 1, nullptr, nullptr, nullptr, nullptr};
+    if (wave_supported(T)) return launch_wave(op, dtype, a, st, between);
     // Pairs pay off when one workgroup per chain would leave at least half of the chip idle.
     static const int cus = [] {
         int dev = 0, n = 0;
@@ -749,6 +691,7 @@ hipError_t launch_chunked_marginals(int dtype, const void* phi, const int32_t* l
                                     hipStream_t st, hipEvent_t between, bool exact_only) {
     const int C = (N + chunk - 1) / chunk;
     ChainArgs a{phi, lengths, B, N, T, ua, ub, Oa, Ob, nullptr, mu, exact_only ? 1 : 0, nullptr, chunk, C, Fv, OF, Gv, OG};
+    if (wave_supported(T)) return launch_wave(1, dtype, a, st, between);
     const PairPlan pair{nullptr, nullptr, dtype};
     const bool aligned = (T % 4) == 0;
     if (dtype == 0)

@@ -1,0 +1,67 @@
+// Arguments of the sum-product chain kernels and the stretch of positions one chain covers
+// (shared by lccrf_chain.hip and lccrf_wave.hip).
+#pragma once
+
+#include "lccrf_device.h"
+
+namespace lccrf {
+
+struct ChainArgs {
+    const void* phi;
+    const int32_t* lengths;
+    int B, N, T;
+    float* ua;   // [B][N][T] normalised forward vectors (base-2 logs)
+    float* ub;   // [B][N][T] normalised backward vectors
+    double* Oa;  // [B][N] forward offsets:  alpha_i = (ua_i + Oa_i) * ln 2
+    double* Ob;  // [B][N] backward offsets
+    float* logZ;
+    float* mu;
+    int exact_only;  // 1: never take the speculative step (tests)
+    const int* only_failed;  // second pass: if set, recompute only the sequences flagged here
+    // Chunked schedule (chunk > 0): workgroup pair v serves chunk c = v % C of sequence v / C, the
+    // tag positions [c chunk, (c+1) chunk), as a chain of its own that starts one position earlier
+    // from the boundary vectors the scan has produced (lccrf_scan.hip).
+    int chunk, C;
+    const float* Fv;   // [B][C][T] alpha at the last position of each chunk, normalised
+    const double* OF;  // [B][C] its offset
+    const float* Gv;   // [B][C][T] beta at the last position of each chunk, normalised
+    const double* OG;  // [B][C]
+};
+
+// The stretch of positions one pair of workgroups handles: all of a sequence, or one chunk.
+struct Span {
+    int b, c;
+    int L;       // clamped length of the sequence
+    int p0, e;   // first and last position of the chain (p0 carries the start vector)
+    bool first;  // p0 is position 0: start from the first row of the first matrix
+    bool last;   // e is the last position of the sequence: beta = 0 there
+    bool empty;  // nothing to do
+};
+
+__device__ __forceinline__ Span make_span(const ChainArgs& a, int v) {
+    Span s;
+    if (a.chunk <= 0) {
+        s.b = v; s.c = 0;
+        s.L = clamp_length(a.lengths, s.b, a.N);
+        s.p0 = 0; s.e = s.L - 1; s.first = true; s.last = true; s.empty = s.L == 0;
+    } else {
+        s.b = v / a.C; s.c = v % a.C;
+        s.L = clamp_length(a.lengths, s.b, a.N);
+        const int t0 = s.c * a.chunk;
+        s.empty = t0 >= s.L;
+        s.first = s.c == 0;
+        s.p0 = s.first ? 0 : t0 - 1;
+        const int t1 = t0 + a.chunk;
+        s.e = (t1 < s.L ? t1 : s.L) - 1;
+        s.last = s.e == s.L - 1;
+    }
+    return s;
+}
+
+// One-wave-per-chain kernels for T <= 32 (lccrf_wave.hip): one pass over all chains of `a`
+// (a.C = 1 for whole sequences).  The first pass stores the vectors of both half chains, the
+// second writes the marginals.  dtype 0: float, 1: bfloat16.
+bool wave_supported(int T);
+hipError_t launch_wave_pass(bool second_pass, int dtype, const ChainArgs& a, hipStream_t st);
+
+}  // namespace lccrf

@@ -210,6 +210,26 @@ __device__ __forceinline__ void walk(int first, int last, int dir, Load load, St
     }
 }
 
+constexpr float kSumLo = 0x1p-60f, kSumHi = 0x1p60f;  // accepted range of a speculative sum
+__device__ __forceinline__ bool sum_in_range(float S) { return S >= kSumLo && S <= kSumHi; }  // false for NaN
+
+// Store 4 consecutive marginals of row s (columns c4 .. c4+3), only those inside the matrix.
+template <bool ALIGNED>
+__device__ __forceinline__ void store4(float* __restrict__ mu_out, int T, int s, int c4,
+                                       float a0, float a1, float a2, float a3) {
+    if (s < T && c4 < T) {
+        float* p = mu_out + (size_t)s * T + c4;
+        if (ALIGNED) {
+            *reinterpret_cast<float4*>(p) = make_float4(a0, a1, a2, a3);
+        } else {
+            p[0] = a0;
+            if (c4 + 1 < T) p[1] = a1;
+            if (c4 + 2 < T) p[2] = a2;
+            if (c4 + 3 < T) p[3] = a3;
+        }
+    }
+}
+
 __device__ __forceinline__ float finite_or_zero(float m) { return (m == LCCRF_NEG_INF) ? 0.0f : m; }
 
 __device__ __forceinline__ int clamp_length(const int32_t* __restrict__ lengths, int b, int N) {

@@ -1,0 +1,478 @@
+// Sum-product chains for small tag sets (T <= 32): one wave per chain, nothing but registers.
+//
+// Same schedule and arithmetic as lccrf_chain.hip (two chains per sequence or per chunk meeting
+// in the middle, pass 1 stores the vectors, pass 2 writes the marginals; speculative
+// uniform-shift step with exact replay; drift feedback), but a matrix of at most 32 x 32 fits one
+// wave, so a step needs no LDS memory and no barrier: its latency is a handful of lane exchanges
+// instead of two workgroup barriers.  That latency is what bounds these shapes (a step moves
+// 1 to 8 KB), both for whole sequences and for the chunks of the scan.
+//
+// Lane mapping for the padded size TP (16 or 32): CG = TP / 4 lanes cover one row with four
+// columns each (16-byte loads), the RG = 64 / CG row groups own R = TP / RG consecutive rows
+// each: lane (rg, cg) holds phi[R rg + k][4 cg + j], k < R, j < 4.
+//
+// A vector of TP entries lives in registers in one of two forms:
+//   column form: lane (rg, cg) holds entries 4 cg + j   (the same in every row group);
+//   row form:    lane (rg, cg) holds entries R rg + k   (the same in every column group).
+// The forward step takes alpha in row form and, after summing over the row groups, leaves the
+// new alpha in column form; the backward step takes beta in column form and leaves the new beta
+// in row form.  Turning one form into the other is a transpose of the 8 x 8 (4 x 16) lane grid:
+// at most four ds_bpermute per step.
+#include "lccrf_chain_args.h"
+#include "lccrf_device.h"
+#include "lccrf_launch.h"
+
+namespace lccrf {
+
+template <int TP>
+struct WGeo {
+    static_assert(TP == 16 || TP == 32, "padded tag-set sizes served by one wave");
+    static constexpr int CG = TP / 4;
+    static constexpr int RG = 64 / CG;
+    static constexpr int R = TP / RG;  // 1 or 4
+};
+
+__device__ __forceinline__ float lane_read(float x, int src_lane) {
+    return __int_as_float(__builtin_amdgcn_ds_bpermute(src_lane << 2, __float_as_int(x)));
+}
+
+template <int TP>
+__device__ __forceinline__ void col_to_row(const float (&vc)[4], float (&vr)[WGeo<TP>::R], int lane) {
+    if constexpr (TP == 32) {
+        // entries 4 rg + k are the four registers of any lane whose column group is rg
+        const int src = (lane & ~7) | (lane >> 3);
+#pragma unroll
+        for (int k = 0; k < WGeo<TP>::R; ++k) vr[k] = lane_read(vc[k], src);
+    } else {
+        // entry rg is register rg % 4 of a lane whose column group is rg / 4; every lane offers
+        // the register its own row group selects and is read by lanes of that same row group
+        const int sel = (lane >> 2) & 3;
+        const float pub = sel == 0 ? vc[0] : sel == 1 ? vc[1] : sel == 2 ? vc[2] : vc[3];
+        vr[0] = lane_read(pub, (lane & ~3) | (lane >> 4));
+    }
+}
+
+template <int TP>
+__device__ __forceinline__ void row_to_col(const float (&vr)[WGeo<TP>::R], float (&vc)[4], int lane) {
+    if constexpr (TP == 32) {
+        // entries 4 cg + j are the four registers of any lane whose row group is cg
+        const int src = ((lane & 7) << 3) | (lane >> 3);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) vc[j] = lane_read(vr[j], src);
+    } else {
+        // entry 4 cg + j is the register of any lane whose row group is 4 cg + j
+        const int cg = lane & 3;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) vc[j] = lane_read(vr[0], ((4 * cg + j) << 2) | cg);
+    }
+}
+
+template <int TP, typename TIN, bool ALIGNED>
+__device__ __forceinline__ void wave_load(const TIN* __restrict__ mat, int T, int lane, float (&v)[WGeo<TP>::R][4]) {
+    using W = WGeo<TP>;
+    const int c4 = 4 * (lane % W::CG), s0 = W::R * (lane / W::CG);
+#pragma unroll
+    for (int k = 0; k < W::R; ++k) {
+        const int s = s0 + k;
+        const TIN* row = mat + (size_t)(s < T ? s : T - 1) * T;
+        if (ALIGNED) {
+            Elem<TIN>::get4(row + (c4 < T ? c4 : T - 4), v[k]);
+        } else {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) v[k][j] = Elem<TIN>::get(row + (c4 + j < T ? c4 + j : T - 1));
+        }
+    }
+}
+
+__device__ __forceinline__ float max4(const float (&x)[4]) { return fmaxf(fmaxf(x[0], x[1]), fmaxf(x[2], x[3])); }
+
+// One forward position: r(t) = log2 sum_s 2^(ua(s) + phi2(s,t)), ua in row form, r in column form.
+// With WITH_MU it also writes mu(s,t) = 2^(ua(s) + phi2(s,t) + ubK(t)) and returns their sum.
+// The speculative form shifts everything by c; it stands only if every sum it made is in range.
+template <int TP, bool WITH_MU, bool ALIGNED>
+__device__ __forceinline__ void wave_fwd_step(float (&v)[WGeo<TP>::R][4], const float (&ua)[WGeo<TP>::R], float c,
+                                              const float (&ubK)[4], float* __restrict__ mu_out, int T, int lane,
+                                              bool exact_only, float (&r)[4], float& tot) {
+    using W = WGeo<TP>;
+    constexpr int R = W::R;
+    const int c4 = 4 * (lane % W::CG), s0 = R * (lane / W::CG);
+    bool accepted = false;
+    if (!exact_only) {
+        float ls[4] = {0.f, 0.f, 0.f, 0.f}, gm[4] = {0.f, 0.f, 0.f, 0.f};
+        if (WITH_MU) {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) gm[j] = ex2(c + ubK[j]);
+        }
+#pragma unroll
+        for (int k = 0; k < R; ++k) {
+            const float uac = ua[k] - c;
+            float e[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                e[j] = ex2(__builtin_fmaf(v[k][j], kLog2e, uac));
+                ls[j] += e[j];
+            }
+            if (WITH_MU) store4<ALIGNED>(mu_out, T, s0 + k, c4, e[0] * gm[0], e[1] * gm[1], e[2] * gm[2], e[3] * gm[3]);
+        }
+        const float part = (ls[0] * gm[0] + ls[1] * gm[1]) + (ls[2] * gm[2] + ls[3] * gm[3]);
+        bool ok = true;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const float S = xor_sum<W::CG, 64>(ls[j]);
+            const bool inm = c4 + j < T;
+            r[j] = inm ? c + lg2(S) : LCCRF_NEG_INF;
+            ok = ok && (!inm || sum_in_range(S));
+        }
+        accepted = __builtin_amdgcn_ballot_w64(!ok) == 0;
+        if (WITH_MU && accepted) tot = xor_sum<1, 64>(part);
+    }
+    if (!accepted) {
+        float lm[4] = {LCCRF_NEG_INF, LCCRF_NEG_INF, LCCRF_NEG_INF, LCCRF_NEG_INF};
+#pragma unroll
+        for (int k = 0; k < R; ++k)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                v[k][j] = __builtin_fmaf(v[k][j], kLog2e, ua[k]);
+                lm[j] = fmaxf(lm[j], v[k][j]);
+            }
+        float M[4], g[4], ls[4] = {0.f, 0.f, 0.f, 0.f}, gm[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            M[j] = xor_max<W::CG, 64>(lm[j]);
+            g[j] = finite_or_zero(M[j]);
+            if (WITH_MU) gm[j] = ex2(g[j] + ubK[j]);
+        }
+#pragma unroll
+        for (int k = 0; k < R; ++k) {
+            float e[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                e[j] = ex2(v[k][j] - g[j]);
+                ls[j] += e[j];
+            }
+            if (WITH_MU) store4<ALIGNED>(mu_out, T, s0 + k, c4, e[0] * gm[0], e[1] * gm[1], e[2] * gm[2], e[3] * gm[3]);
+        }
+        if (WITH_MU) tot = xor_sum<1, 64>((ls[0] * gm[0] + ls[1] * gm[1]) + (ls[2] * gm[2] + ls[3] * gm[3]));
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const float S = xor_sum<W::CG, 64>(ls[j]);
+            r[j] = (c4 + j < T) ? M[j] + lg2(S) : LCCRF_NEG_INF;  // M = -inf gives S = 0: -inf
+        }
+    }
+}
+
+// One backward position: r(s) = log2 sum_t 2^(phi2(s,t) + ub(t)), ub in column form, r in row form.
+template <int TP, bool WITH_MU, bool ALIGNED>
+__device__ __forceinline__ void wave_bwd_step(float (&v)[WGeo<TP>::R][4], const float (&ub)[4], float c,
+                                              const float (&uaK)[WGeo<TP>::R], float* __restrict__ mu_out, int T,
+                                              int lane, bool exact_only, float (&r)[WGeo<TP>::R], float& tot) {
+    using W = WGeo<TP>;
+    constexpr int R = W::R;
+    const int c4 = 4 * (lane % W::CG), s0 = R * (lane / W::CG);
+    bool accepted = false;
+    if (!exact_only) {
+        const float ubc[4] = {ub[0] - c, ub[1] - c, ub[2] - c, ub[3] - c};
+        float part = 0.f;
+        bool ok = true;
+#pragma unroll
+        for (int k = 0; k < R; ++k) {
+            float e[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) e[j] = ex2(__builtin_fmaf(v[k][j], kLog2e, ubc[j]));
+            const float Sl = (e[0] + e[1]) + (e[2] + e[3]);
+            if (WITH_MU) {
+                const float f = ex2(c + uaK[k]);
+                store4<ALIGNED>(mu_out, T, s0 + k, c4, e[0] * f, e[1] * f, e[2] * f, e[3] * f);
+                part += Sl * f;
+            }
+            const float S = xor_sum<1, W::CG>(Sl);
+            const bool inm = s0 + k < T;
+            r[k] = inm ? c + lg2(S) : LCCRF_NEG_INF;
+            ok = ok && (!inm || sum_in_range(S));
+        }
+        accepted = __builtin_amdgcn_ballot_w64(!ok) == 0;
+        if (WITH_MU && accepted) tot = xor_sum<1, 64>(part);
+    }
+    if (!accepted) {
+        float part = 0.f;
+#pragma unroll
+        for (int k = 0; k < R; ++k) {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) v[k][j] = __builtin_fmaf(v[k][j], kLog2e, ub[j]);
+            const float m = xor_max<1, W::CG>(max4(v[k]));
+            const float g = finite_or_zero(m);
+            float e[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) e[j] = ex2(v[k][j] - g);
+            const float Sl = (e[0] + e[1]) + (e[2] + e[3]);
+            if (WITH_MU) {
+                const float f = ex2(g + uaK[k]);
+                store4<ALIGNED>(mu_out, T, s0 + k, c4, e[0] * f, e[1] * f, e[2] * f, e[3] * f);
+                part += Sl * f;
+            }
+            r[k] = (s0 + k < T) ? m + lg2(xor_sum<1, W::CG>(Sl)) : LCCRF_NEG_INF;
+        }
+        if (WITH_MU) tot = xor_sum<1, 64>(part);
+    }
+}
+
+// -log2 of the sum of the marginals the last step wrote (0 if nothing usable was written).
+__device__ __forceinline__ float drift_of(float tot) { return (tot > 0.5f && tot < 2.0f) ? -lg2(tot) : 0.f; }
+
+// Tiles in flight per wave: more in the first pass, whose slots are smaller (no stored vector rides along).
+constexpr int wave_ring_depth(int TP, bool second_pass) { return second_pass ? (TP == 16 ? 6 : 4) : (TP == 16 ? 8 : 6); }
+
+// ---------------------------------------------------------------------------------------
+// Pass 1: both half chains, vectors stored.
+template <int TP, typename TIN, bool ALIGNED>
+__global__ __launch_bounds__(64) void wave_half_kernel(ChainArgs a) {
+    using W = WGeo<TP>;
+    constexpr int R = W::R, PF = wave_ring_depth(TP, false);
+    const int lane = threadIdx.x, cg = lane % W::CG, rg = lane / W::CG, c4 = 4 * cg, s0 = R * rg;
+    const int dir = blockIdx.x & 1;
+    const Span sp = make_span(a, blockIdx.x >> 1);
+    if (sp.empty) return;
+    const int b = sp.b, N = a.N, T = a.T;
+    const int p0 = sp.p0, e = sp.e;
+    const int h = p0 + (e - p0 + 1) / 2;
+    const size_t TT = (size_t)T * T, vb = (size_t)b * N;
+    const TIN* phib = static_cast<const TIN*>(a.phi) + (size_t)b * N * TT;
+    const bool exact_only = a.exact_only != 0;
+    float ring[PF][R][4];
+    auto load = [&](int i, int slot) { wave_load<TP, TIN, ALIGNED>(phib + (size_t)i * TT, T, lane, ring[slot]); };
+    const float none4[4] = {0.f, 0.f, 0.f, 0.f};
+    float noneR[R];
+#pragma unroll
+    for (int k = 0; k < R; ++k) noneR[k] = 0.f;
+    float tot = 0.f;
+    double O = 0.0;
+
+    if (dir == 0) {
+        float vc[4];  // alpha, column form
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int t = c4 + j;
+            vc[j] = LCCRF_NEG_INF;
+            if (t < T) vc[j] = sp.first ? Elem<TIN>::get(phib + t) * kLog2e : a.Fv[((size_t)b * a.C + sp.c - 1) * T + t];
+        }
+        if (!sp.first) O = a.OF[(size_t)b * a.C + sp.c - 1];
+        auto settle = [&](int pos) {  // normalise the vector of position `pos` and store it
+            const float d = finite_or_zero(xor_max<1, W::CG>(max4(vc)));
+            O += (double)d;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) vc[j] -= d;
+            if (rg == 0) {
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    if (c4 + j < T) a.ua[(vb + pos) * T + c4 + j] = vc[j];
+            }
+            if (lane == 0) a.Oa[vb + pos] = O;
+            return d;
+        };
+        walk<PF>(p0 + 1, h, +1, load, [&](int i, int slot) {
+            const float d = settle(i - 1);
+            float ua[R];
+            col_to_row<TP>(vc, ua, lane);
+            wave_fwd_step<TP, false, ALIGNED>(ring[slot], ua, d, none4, nullptr, T, lane, exact_only, vc, tot);
+        });
+        settle(h);
+    } else {
+        float vr[R];  // beta, row form
+#pragma unroll
+        for (int k = 0; k < R; ++k) {
+            const int s = s0 + k;
+            vr[k] = LCCRF_NEG_INF;
+            if (s < T) vr[k] = sp.last ? 0.f : a.Gv[((size_t)b * a.C + sp.c) * T + s];
+        }
+        if (!sp.last) O = a.OG[(size_t)b * a.C + sp.c];
+        auto settle = [&](int pos) {
+            float m = vr[0];
+#pragma unroll
+            for (int k = 1; k < R; ++k) m = fmaxf(m, vr[k]);
+            const float d = finite_or_zero(xor_max<W::CG, 64>(m));
+            O += (double)d;
+#pragma unroll
+            for (int k = 0; k < R; ++k) vr[k] -= d;
+            if (cg == 0) {
+#pragma unroll
+                for (int k = 0; k < R; ++k)
+                    if (s0 + k < T) a.ub[(vb + pos) * T + s0 + k] = vr[k];
+            }
+            if (lane == 0) a.Ob[vb + pos] = O;
+            return d;
+        };
+        walk<PF>(e, h + 1, -1, load, [&](int i, int slot) {
+            const float d = settle(i);
+            float ub[4];
+            row_to_col<TP>(vr, ub, lane);
+            wave_bwd_step<TP, false, ALIGNED>(ring[slot], ub, d, noneR, nullptr, T, lane, exact_only, vr, tot);
+        });
+        settle(h);
+    }
+}
+
+// ---------------------------------------------------------------------------------------
+// Pass 2: both chains continue past the meeting point and write the marginals.
+template <int TP, typename TIN, bool ALIGNED>
+__global__ __launch_bounds__(64) void wave_marginal_kernel(ChainArgs a) {
+    using W = WGeo<TP>;
+    constexpr int R = W::R, PF = wave_ring_depth(TP, true);
+    const int lane = threadIdx.x, cg = lane % W::CG, rg = lane / W::CG, c4 = 4 * cg, s0 = R * rg;
+    const int dir = blockIdx.x & 1;
+    const Span sp = make_span(a, blockIdx.x >> 1);
+    const int b = sp.b, N = a.N, T = a.T, L = sp.L;
+    const size_t TT = (size_t)T * T, vb = (size_t)b * N;
+    float* mub = a.mu + (size_t)b * N * TT;
+    const bool exact_only = a.exact_only != 0;
+
+    if (dir == 0) {
+        // positions past the end carry no edge: their marginals are zero (a chunk clears its own range)
+        const int zfrom = a.chunk > 0 ? (sp.c * a.chunk > L ? sp.c * a.chunk : L) : L;
+        const int zto = a.chunk > 0 ? ((sp.c + 1) * a.chunk < N ? (sp.c + 1) * a.chunk : N) : N;
+        const size_t z0 = (size_t)zfrom * TT, z1 = (size_t)(zto > zfrom ? zto : zfrom) * TT;
+        if (ALIGNED) {
+            float4* p = reinterpret_cast<float4*>(mub);
+            for (size_t k = z0 / 4 + lane; k < z1 / 4; k += 64) p[k] = make_float4(0.f, 0.f, 0.f, 0.f);
+        } else {
+            for (size_t k = z0 + lane; k < z1; k += 64) mub[k] = 0.f;
+        }
+    }
+    if (L == 0) {
+        if (dir == 0 && sp.c == 0 && lane == 0 && a.logZ) a.logZ[b] = 0.f;
+        return;
+    }
+    if (sp.empty) return;
+    const int p0 = sp.p0, e = sp.e;
+    const int h = p0 + (e - p0 + 1) / 2;
+    const TIN* phib = static_cast<const TIN*>(a.phi) + (size_t)b * N * TT;
+
+    // log2 Z from the two vectors stored for the meeting position
+    double lz2;
+    {
+        float z[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int t = c4 + j;
+            z[j] = (t < T) ? a.ua[(vb + h) * T + t] + a.ub[(vb + h) * T + t] : LCCRF_NEG_INF;
+        }
+        const float M = xor_max<1, W::CG>(max4(z));
+        const float g = finite_or_zero(M);
+        const float S = xor_sum<1, W::CG>((ex2(z[0] - g) + ex2(z[1] - g)) + (ex2(z[2] - g) + ex2(z[3] - g)));
+        lz2 = (double)(M + lg2(S)) + a.Oa[vb + h] + a.Ob[vb + h];
+    }
+    const bool feasible = lz2 > -1.0e300;  // false: no path has a finite score, marginals are 0
+    if (dir == 0 && sp.c == 0 && lane == 0 && a.logZ) a.logZ[b] = (float)(lz2 * kLn2);
+
+    float ring[PF][R][4];
+    float kappa = 0.f, tot = 0.f;
+
+    if (dir == 0) {
+        double O = a.Oa[vb + h];
+        float vc[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) vc[j] = (c4 + j < T) ? a.ua[(vb + h) * T + c4 + j] : LCCRF_NEG_INF;
+        float aux[PF][4];
+        double ob[PF];
+        auto load = [&](int i, int slot) {
+            wave_load<TP, TIN, ALIGNED>(phib + (size_t)i * TT, T, lane, ring[slot]);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) aux[slot][j] = a.ub[(vb + i) * T + (c4 + j < T ? c4 + j : T - 1)];
+            ob[slot] = a.Ob[vb + i];
+        };
+        walk<PF>(h + 1, e, +1, load, [&](int i, int slot) {
+            const float d = finite_or_zero(xor_max<1, W::CG>(max4(vc)));
+            kappa += drift_of(tot);
+            O += (double)d;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) vc[j] -= d;
+            float ua[R];
+            col_to_row<TP>(vc, ua, lane);
+            const float K = feasible ? (float)(O + ob[slot] - lz2) + kappa : LCCRF_NEG_INF;
+            float ubK[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) ubK[j] = (c4 + j < T) ? aux[slot][j] + K : LCCRF_NEG_INF;
+            wave_fwd_step<TP, true, ALIGNED>(ring[slot], ua, d, ubK, mub + (size_t)i * TT, T, lane, exact_only, vc, tot);
+        });
+    } else {
+        double O = a.Ob[vb + h];
+        float vr[R];
+#pragma unroll
+        for (int k = 0; k < R; ++k) vr[k] = (s0 + k < T) ? a.ub[(vb + h) * T + s0 + k] : LCCRF_NEG_INF;
+        float aux[PF][R];
+        double oa[PF];
+        auto load = [&](int i, int slot) {
+            wave_load<TP, TIN, ALIGNED>(phib + (size_t)i * TT, T, lane, ring[slot]);
+#pragma unroll
+            for (int k = 0; k < R; ++k) aux[slot][k] = a.ua[(vb + i - 1) * T + (s0 + k < T ? s0 + k : T - 1)];
+            oa[slot] = a.Oa[vb + i - 1];
+        };
+        walk<PF>(h, p0 + 1, -1, load, [&](int i, int slot) {
+            float m = vr[0];
+#pragma unroll
+            for (int k = 1; k < R; ++k) m = fmaxf(m, vr[k]);
+            const float d = finite_or_zero(xor_max<W::CG, 64>(m));
+            kappa += drift_of(tot);
+            O += (double)d;
+#pragma unroll
+            for (int k = 0; k < R; ++k) vr[k] -= d;
+            float ub[4];
+            row_to_col<TP>(vr, ub, lane);
+            const float K = feasible ? (float)(oa[slot] + O - lz2) + kappa : LCCRF_NEG_INF;
+            float uaK[R];
+#pragma unroll
+            for (int k = 0; k < R; ++k) uaK[k] = (s0 + k < T) ? aux[slot][k] + K : LCCRF_NEG_INF;
+            wave_bwd_step<TP, true, ALIGNED>(ring[slot], ub, d, uaK, mub + (size_t)i * TT, T, lane, exact_only, vr, tot);
+        });
+        // position 0: p(y_0 = t) = softmax_t(alpha_0(t) + beta_0(t)) in row 0, zeros elsewhere
+        if (!sp.first) return;
+        for (int k = T + lane; k < (int)TT; k += 64) mub[k] = 0.f;
+        float z[R], m = LCCRF_NEG_INF;
+#pragma unroll
+        for (int k = 0; k < R; ++k) {
+            z[k] = (s0 + k < T) ? a.ua[vb * T + s0 + k] + vr[k] : LCCRF_NEG_INF;
+            m = fmaxf(m, z[k]);
+        }
+        m = finite_or_zero(xor_max<W::CG, 64>(m));
+        float S = 0.f;
+#pragma unroll
+        for (int k = 0; k < R; ++k) S += ex2(z[k] - m);
+        S = xor_sum<W::CG, 64>(S);
+        const float cnorm = (feasible && S > 0.f) ? 1.0f / S : 0.f;
+        if (cg == 0) {
+#pragma unroll
+            for (int k = 0; k < R; ++k)
+                if (s0 + k < T) mub[s0 + k] = cnorm * ex2(z[k] - m);
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------
+bool wave_supported(int T) { return T >= 1 && T <= 32; }
+
+template <int TP, typename TIN, bool ALIGNED>
+static hipError_t launch_wave_tp(bool second_pass, const ChainArgs& a, hipStream_t st) {
+    const dim3 grid(2 * a.B * a.C);
+    if (second_pass)
+        hipLaunchKernelGGL((wave_marginal_kernel<TP, TIN, ALIGNED>), grid, dim3(64), 0, st, a);
+    else
+        hipLaunchKernelGGL((wave_half_kernel<TP, TIN, ALIGNED>), grid, dim3(64), 0, st, a);
+    return hipGetLastError();
+}
+
+// One pass over all chains of `a` (a.C = 1 for whole sequences): the first stores the vectors of
+// both half chains, the second writes the marginals.
+hipError_t launch_wave_pass(bool second_pass, int dtype, const ChainArgs& a, hipStream_t st) {
+    const bool aligned = (a.T % 4) == 0;
+    if (a.T <= 16) {
+        if (dtype == 0)
+            return aligned ? launch_wave_tp<16, float, true>(second_pass, a, st) : launch_wave_tp<16, float, false>(second_pass, a, st);
+        return aligned ? launch_wave_tp<16, uint16_t, true>(second_pass, a, st)
+                       : launch_wave_tp<16, uint16_t, false>(second_pass, a, st);
+    }
+    if (dtype == 0)
+        return aligned ? launch_wave_tp<32, float, true>(second_pass, a, st) : launch_wave_tp<32, float, false>(second_pass, a, st);
+    return aligned ? launch_wave_tp<32, uint16_t, true>(second_pass, a, st)
+                   : launch_wave_tp<32, uint16_t, false>(second_pass, a, st);
+}
+
+}  // namespace lccrf
