@@ -254,16 +254,31 @@ __device__ __forceinline__ void bwd_fast(ChainSmem<G>& sm, int buf, int flag, in
     }
     float wm = LCCRF_NEG_INF;
     bool ok = true;
+    if constexpr (ITEMS % 4 == 0 && G::LPR >= 16) {
+        // four rows at a time: each lane ends up with the complete sum of one of them
+        const int kk = 2 * (lane & 1) + ((lane >> 1) & 1);
 #pragma unroll
-    for (int k = 0; k < ITEMS; ++k) {
-        const float Sk = xor_sum<1, G::LPR>(S[k]);
-        const int s = r0 + k * G::RPP;
-        const float r = (s < T) ? c + lg2(Sk) : LCCRF_NEG_INF;
-        if (c4 == 0 && s < T) sm.rvec[buf ^ 1][s] = r;
-        ok = ok && (s >= T || sum_in_range(Sk));
-        wm = fmaxf(wm, r);
+        for (int k0 = 0; k0 < ITEMS; k0 += 4) {
+            const float Sk = reduce4_over_lanes<G::LPR>(S[k0], S[k0 + 1], S[k0 + 2], S[k0 + 3], lane);
+            const int s = r0 + (k0 + kk) * G::RPP;
+            const float r = (s < T) ? c + lg2(Sk) : LCCRF_NEG_INF;
+            if ((tid % G::LPR) < 4 && s < T) sm.rvec[buf ^ 1][s] = r;
+            ok = ok && (s >= T || sum_in_range(Sk));
+            wm = fmaxf(wm, r);
+        }
+        wm = xor_max<1, 4>(wm);
+    } else {
+#pragma unroll
+        for (int k = 0; k < ITEMS; ++k) {
+            const float Sk = xor_sum<1, G::LPR>(S[k]);
+            const int s = r0 + k * G::RPP;
+            const float r = (s < T) ? c + lg2(Sk) : LCCRF_NEG_INF;
+            if (c4 == 0 && s < T) sm.rvec[buf ^ 1][s] = r;
+            ok = ok && (s >= T || sum_in_range(Sk));
+            wm = fmaxf(wm, r);
+        }
     }
-    wm = xor_max<G::LPR, 64>(wm);  // every lane of a row already holds the row's r
+    wm = xor_max<G::LPR, 64>(wm);  // lanes of other row groups hold other rows' results
     if (lane == 0) sm.wmax[buf ^ 1][wave] = wm;
     if (!__all(ok) && lane == 0) sm.bad[flag] = 1;
     if (WITH_MU) {
@@ -357,6 +372,146 @@ __device__ __forceinline__ void bwd_advance(ChainSmem<G>& sm, int& buf, int& nst
 }
 
 // ---------------------------------------------------------------------------------------
+// Forward half chain for 64 < T <= 128 (T % 4 == 0) with the tile turned through LDS memory.
+//
+// With rows spread over all 16 waves, the forward step has to merge 16 partial column sums
+// through LDS behind a second barrier while 14 waves wait.  Here every tile is written to LDS
+// as it arrives (coalesced rows, one position ahead of its use) and read back so that a wave
+// owns 8 complete columns: the sum over rows never leaves the wave, the step has one barrier
+// like the backward step, and the exact replay needs no cross-wave merge either.
+// Lane l of wave w holds rows (l % 32) + 32 k, k < 4, of columns 8 w + 4 (l / 32) + j, j < 4.
+template <typename G, bool ALIGNED, int PF>
+constexpr bool half_turns() { return G::LPR == 32 && G::WAVES == 16 && G::ITEMS == 4 && ALIGNED && PF == 4; }
+constexpr int kTurnStride = 132;  // floats per LDS row: 128 + 4 keeps 16-byte accesses conflict free
+constexpr int kTurnFloats = 2 * 128 * kTurnStride;
+
+template <typename G, typename TIN, int PF>
+__device__ __forceinline__ void forward_half_turned(ChainSmem<G>& sm, float* __restrict__ tiles, const ChainArgs& a,
+                                                    const Span& sp, int tid) {
+    static_assert(G::LPR == 32 && G::WAVES == 16 && G::ITEMS == 4 && PF == 4, "laid out for 1024 threads, T <= 128");
+    const int lane = tid & 63, wave = tid >> 6;
+    const int b = sp.b, N = a.N, T = a.T;
+    const int p0 = sp.p0, h = meeting_point(sp.p0, sp.e);
+    const int c4 = 4 * (tid % 32), r0 = tid / 32;
+    const size_t TT = (size_t)T * T, vb = (size_t)b * N;
+    const TIN* phib = static_cast<const TIN*>(a.phi) + (size_t)b * N * TT;
+    const bool exact_only = a.exact_only != 0;
+    const int rowl = lane & 31, colw = 8 * wave + 4 * (lane >> 5);
+    const int kk = 2 * (lane & 1) + ((lane >> 1) & 1);  // the column reduce4_over_lanes leaves in this lane
+
+    double O = 0.0;
+    {
+        float v0 = LCCRF_NEG_INF;
+        if (tid < T) v0 = sp.first ? Elem<TIN>::get(phib + tid) * kLog2e : a.Fv[((size_t)b * a.C + sp.c - 1) * T + tid];
+        if (!sp.first) O = a.OF[(size_t)b * a.C + sp.c - 1];
+        publish_columns<G>(sm, 0, tid, v0);
+    }
+    const int first = p0 + 1, n = h - p0;  // positions first .. h
+    int buf = 0, nstep = 0;
+    if (n > 0) {
+        float ring[PF][4][4];
+        auto load = [&](int i, int slot) { load_tile<G, TIN, true>(phib + (size_t)i * TT, T, c4, r0, ring[slot]); };
+        auto to_lds = [&](int slot, int wb) {
+#pragma unroll
+            for (int k = 0; k < 4; ++k)
+                *reinterpret_cast<float4*>(&tiles[(wb * 128 + r0 + 32 * k) * kTurnStride + c4]) =
+                    make_float4(ring[slot][k][0], ring[slot][k][1], ring[slot][k][2], ring[slot][k][3]);
+        };
+#pragma unroll
+        for (int p = 0; p < PF; ++p) load(first + (p < n ? p : n - 1), p);
+        to_lds(0, 0);
+        load(first + (PF < n ? PF : n - 1), 0);
+        __syncthreads();
+        int done = 0;
+        bool running = true;
+        while (running) {
+#pragma unroll
+            for (int p = 0; p < PF; ++p) {
+                const int i = first + done;
+                const int rb = p & 1, nslot = (p + 1) % PF;
+                // this wave's columns of tile i, four rows at a time
+                const float* mine = &tiles[(rb * 128 + rowl) * kTurnStride + colw];
+                const float d = read_shift<G>(sm, buf);
+                O += (double)d;
+                float ua[4];
+#pragma unroll
+                for (int k = 0; k < 4; ++k) ua[k] = sm.rvec[buf][rowl + 32 * k] - d;  // -inf for rows >= T
+                if (tid < T) a.ua[(vb + i - 1) * T + tid] = sm.rvec[buf][tid] - d;
+                if (tid == 0) a.Oa[vb + i - 1] = O;
+                // tile i + 1 goes to the other LDS buffer; its ring slot takes tile i + 1 + PF
+                to_lds(nslot, nslot & 1);
+                {
+                    const int ahead = done + 1 + PF;
+                    load(first + (ahead < n ? ahead : n - 1), nslot);
+                }
+                const int flag = nstep & 3;
+                if (tid == 0) sm.bad[(nstep + 1) & 3] = 0;
+                if (!exact_only) {
+                    float ls[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                    for (int k = 0; k < 4; ++k) {
+                        const float uac = ua[k] - d;  // shift c = d, the previous normaliser
+                        const float4 q = *reinterpret_cast<const float4*>(mine + 32 * k * kTurnStride);
+                        ls[0] += ex2(__builtin_fmaf(q.x, kLog2e, uac));
+                        ls[1] += ex2(__builtin_fmaf(q.y, kLog2e, uac));
+                        ls[2] += ex2(__builtin_fmaf(q.z, kLog2e, uac));
+                        ls[3] += ex2(__builtin_fmaf(q.w, kLog2e, uac));
+                    }
+                    const float S = reduce4_over_lanes<32>(ls[0], ls[1], ls[2], ls[3], lane);
+                    const int col = colw + kk;
+                    const float r = (col < T) ? d + lg2(S) : LCCRF_NEG_INF;
+                    if (rowl < 4) sm.rvec[buf ^ 1][col] = r;
+                    const float wm = xor_max<32, 64>(xor_max<1, 4>(r));
+                    if (lane == 0) sm.wmax[buf ^ 1][wave] = wm;
+                    const bool ok = col >= T || sum_in_range(S);
+                    if (!__all(ok) && lane == 0) sm.bad[flag] = 1;
+                    __syncthreads();
+                }
+                if (exact_only || sm.bad[flag] != 0) {
+                    // exact step: every log-sum-exp against its own maximum, all inside the wave
+                    float v[4][4];
+                    float lm[4] = {LCCRF_NEG_INF, LCCRF_NEG_INF, LCCRF_NEG_INF, LCCRF_NEG_INF};
+#pragma unroll
+                    for (int k = 0; k < 4; ++k) {
+                        const float4 q = *reinterpret_cast<const float4*>(mine + 32 * k * kTurnStride);
+                        v[k][0] = __builtin_fmaf(q.x, kLog2e, ua[k]);
+                        v[k][1] = __builtin_fmaf(q.y, kLog2e, ua[k]);
+                        v[k][2] = __builtin_fmaf(q.z, kLog2e, ua[k]);
+                        v[k][3] = __builtin_fmaf(q.w, kLog2e, ua[k]);
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) lm[j] = fmaxf(lm[j], v[k][j]);
+                    }
+                    float r[4];
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        const float M = xor_max<1, 32>(lm[j]);
+                        const float g = finite_or_zero(M);
+                        float Sl = 0.f;
+#pragma unroll
+                        for (int k = 0; k < 4; ++k) Sl += ex2(v[k][j] - g);
+                        r[j] = (colw + j < T) ? M + lg2(xor_sum<1, 32>(Sl)) : LCCRF_NEG_INF;
+                    }
+                    __syncthreads();  // nobody still reads the rejected vector
+                    if (rowl == 0) *reinterpret_cast<float4*>(&sm.rvec[buf ^ 1][colw]) = make_float4(r[0], r[1], r[2], r[3]);
+                    const float wm = xor_max<32, 64>(fmaxf(fmaxf(r[0], r[1]), fmaxf(r[2], r[3])));
+                    if (lane == 0) sm.wmax[buf ^ 1][wave] = wm;
+                    __syncthreads();
+                }
+                buf ^= 1;
+                ++nstep;
+                if (++done >= n) { running = false; break; }
+            }
+        }
+    } else {
+        __syncthreads();
+    }
+    const float d = read_shift<G>(sm, buf);
+    O += (double)d;
+    if (tid < T) a.ua[(vb + h) * T + tid] = sm.rvec[buf][tid] - d;
+    if (tid == 0) a.Oa[vb + h] = O;
+}
+
+// ---------------------------------------------------------------------------------------
 // Pass 1: both half chains, vectors stored, nothing else written.
 template <typename G, typename TIN, bool ALIGNED, int PF>
 __global__ __launch_bounds__(G::W) void chain_half_kernel(ChainArgs a) {
@@ -369,7 +524,7 @@ __global__ __launch_bounds__(G::W) void chain_half_kernel(ChainArgs a) {
     const int N = a.N, T = a.T;
     if (sp.empty) return;
     const int p0 = sp.p0, e = sp.e;
-    const int h = p0 + (e - p0 + 1) / 2;
+    const int h = meeting_point(p0, e);
     const int c4 = 4 * (tid % G::LPR), r0 = tid / G::LPR;
     const TIN* phib = static_cast<const TIN*>(a.phi) + (size_t)b * N * T * T;
     const size_t TT = (size_t)T * T;
@@ -378,6 +533,13 @@ __global__ __launch_bounds__(G::W) void chain_half_kernel(ChainArgs a) {
 
     smem_init<G>(sm, tid);
     __syncthreads();
+    if constexpr (half_turns<G, ALIGNED, PF>()) {
+        if (dir == 0) {
+            extern __shared__ __attribute__((aligned(16))) float turn_tiles[];
+            forward_half_turned<G, TIN, PF>(sm, turn_tiles, a, sp, tid);
+            return;
+        }
+    }
     float ring[PF][ITEMS][4];
     const float dummy4[4] = {0.f, 0.f, 0.f, 0.f};
     float dummyI[ITEMS];
@@ -494,7 +656,7 @@ __global__ __launch_bounds__(G::W) void chain_marginal_kernel(ChainArgs a) {
     }
     if (sp.empty) return;
     const int p0 = sp.p0, e = sp.e;
-    const int h = p0 + (e - p0 + 1) / 2;
+    const int h = meeting_point(p0, e);
     const int c4 = 4 * (tid % G::LPR), r0 = tid / G::LPR;
     const TIN* phib = static_cast<const TIN*>(a.phi) + (size_t)b * N * TT;
 
@@ -590,7 +752,7 @@ __global__ __launch_bounds__(64) void logz_combine_kernel(ChainArgs a) {
         if (lane == 0) a.logZ[b] = 0.f;
         return;
     }
-    const int h = L / 2;
+    const int h = meeting_point(0, L - 1);
     const size_t vb = (size_t)b * N;
     const float* ua = a.ua + (vb + h) * T;
     const float* ub = a.ub + (vb + h) * T;
@@ -614,8 +776,16 @@ struct PairPlan {
 
 template <typename G, typename TIN, bool ALIGNED, int PF1, int PF2>
 static hipError_t launch_geo(int op, ChainArgs a, hipStream_t st, hipEvent_t between, const PairPlan& pair) {
-    hipLaunchKernelGGL((chain_half_kernel<G, TIN, ALIGNED, PF1>), dim3(2 * a.B * a.C), dim3(G::W), 0, st, a);
-    hipError_t e = hipGetLastError();
+    hipError_t e = hipSuccess;
+    size_t turn_bytes = 0;
+    if constexpr (half_turns<G, ALIGNED, PF1>()) {
+        turn_bytes = kTurnFloats * sizeof(float);
+        e = hipFuncSetAttribute(reinterpret_cast<const void*>(&chain_half_kernel<G, TIN, ALIGNED, PF1>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)turn_bytes);
+        if (e != hipSuccess) return e;
+    }
+    hipLaunchKernelGGL((chain_half_kernel<G, TIN, ALIGNED, PF1>), dim3(2 * a.B * a.C), dim3(G::W), turn_bytes, st, a);
+    e = hipGetLastError();
     if (e != hipSuccess) return e;
     if (between) {
         e = hipEventRecord(between, st);

@@ -118,6 +118,21 @@ __device__ __forceinline__ void store_tile(float* __restrict__ mat, int T, int c
     }
 }
 
+// Cross-lane moves on the DPP path (no LDS).  Written with a zero `old` value and bound_ctrl set,
+// the form the compiler can fold into the consuming add or max (v_add_f32_dpp) instead of a copy,
+// a hazard nop and a separate move.
+constexpr int kDppQuadXor1 = 0xB1;     // quad_perm [1,0,3,2]
+constexpr int kDppQuadXor2 = 0x4E;     // quad_perm [2,3,0,1]
+constexpr int kDppRowRor4 = 0x124;     // rotate right by 4 within a row of 16 lanes
+constexpr int kDppRowRor8 = 0x128;
+constexpr int kDppHalfMirror = 0x141;  // lane i <-> 7 - i within each group of 8 lanes
+template <int CTRL>
+__device__ __forceinline__ float dpp(float x) {
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), CTRL, 0xF, 0xF, true));
+}
+template <int CTRL>
+__device__ __forceinline__ int dpp_i(int x) { return __builtin_amdgcn_update_dpp(0, x, CTRL, 0xF, 0xF, true); }
+
 // Value held by lane (id ^ OFF) of the same wave, without touching LDS memory where the
 // hardware offers a cross-lane path: DPP quad permutes and row rotates inside a row of 16
 // lanes, the LDS crossbar swizzle for a distance of 4, and the gfx950 permlane swaps
@@ -125,10 +140,10 @@ __device__ __forceinline__ void store_tile(float* __restrict__ mat, int T, int c
 template <int OFF>
 __device__ __forceinline__ int lane_xor_i(int x) {
     static_assert(OFF == 1 || OFF == 2 || OFF == 4 || OFF == 8 || OFF == 16 || OFF == 32, "power of two < 64");
-    if (OFF == 1) return __builtin_amdgcn_update_dpp(x, x, 0xB1, 0xF, 0xF, false);   // quad_perm [1,0,3,2]
-    if (OFF == 2) return __builtin_amdgcn_update_dpp(x, x, 0x4E, 0xF, 0xF, false);   // quad_perm [2,3,0,1]
+    if (OFF == 1) return dpp_i<kDppQuadXor1>(x);
+    if (OFF == 2) return dpp_i<kDppQuadXor2>(x);
     if (OFF == 4) return __builtin_amdgcn_ds_swizzle(x, 0x101F);                     // bit mode, xor 4
-    if (OFF == 8) return __builtin_amdgcn_update_dpp(x, x, 0x128, 0xF, 0xF, false);  // row_ror:8
+    if (OFF == 8) return dpp_i<kDppRowRor8>(x);
     const int lane = __lane_id();
     if (OFF == 16) {
         const auto r = __builtin_amdgcn_permlane16_swap(x, x, false, false);
@@ -149,12 +164,15 @@ __device__ __forceinline__ double lane_xor(double x) {
 // All-reduce over the lanes of a wave whose ids differ only in the bits [LO, HI) (LO, HI
 // powers of two, LO >= HI means a single lane: nothing to do).  Every lane of a group ends
 // with the bit-identical result (both partners of an exchange add the same two numbers).
+// Once the four lanes of every quad hold the same value (LO = 1), the partner at distance 4 is
+// reached by mirroring the group of 8 lanes (lane i takes 7 - i, which sits in the other quad
+// and holds that quad's value): a DPP move instead of a trip through the LDS crossbar.
 template <int LO, int HI>
 __device__ __forceinline__ float xor_max(float x) {
-    if (LO <= 1 && 1 < HI) x = fmaxf(x, lane_xor<1>(x));
-    if (LO <= 2 && 2 < HI) x = fmaxf(x, lane_xor<2>(x));
-    if (LO <= 4 && 4 < HI) x = fmaxf(x, lane_xor<4>(x));
-    if (LO <= 8 && 8 < HI) x = fmaxf(x, lane_xor<8>(x));
+    if (LO <= 1 && 1 < HI) x = fmaxf(x, dpp<kDppQuadXor1>(x));
+    if (LO <= 2 && 2 < HI) x = fmaxf(x, dpp<kDppQuadXor2>(x));
+    if (LO <= 4 && 4 < HI) x = fmaxf(x, LO <= 1 ? dpp<kDppHalfMirror>(x) : lane_xor<4>(x));
+    if (LO <= 8 && 8 < HI) x = fmaxf(x, dpp<kDppRowRor8>(x));
     if (LO <= 16 && 16 < HI) {  // both halves of the swapped pair: no select needed for a symmetric op
         const auto r = __builtin_amdgcn_permlane16_swap(__float_as_int(x), __float_as_int(x), false, false);
         x = fmaxf(__int_as_float(r[0]), __int_as_float(r[1]));
@@ -167,15 +185,41 @@ __device__ __forceinline__ float xor_max(float x) {
 }
 template <int LO, int HI>
 __device__ __forceinline__ float xor_sum(float x) {
-    if (LO <= 1 && 1 < HI) x += lane_xor<1>(x);
-    if (LO <= 2 && 2 < HI) x += lane_xor<2>(x);
-    if (LO <= 4 && 4 < HI) x += lane_xor<4>(x);
-    if (LO <= 8 && 8 < HI) x += lane_xor<8>(x);
+    if (LO <= 1 && 1 < HI) x += dpp<kDppQuadXor1>(x);
+    if (LO <= 2 && 2 < HI) x += dpp<kDppQuadXor2>(x);
+    if (LO <= 4 && 4 < HI) x += LO <= 1 ? dpp<kDppHalfMirror>(x) : lane_xor<4>(x);
+    if (LO <= 8 && 8 < HI) x += dpp<kDppRowRor8>(x);
     if (LO <= 16 && 16 < HI) {
         const auto r = __builtin_amdgcn_permlane16_swap(__float_as_int(x), __float_as_int(x), false, false);
         x = __int_as_float(r[0]) + __int_as_float(r[1]);
     }
     if (LO <= 32 && 32 < HI) {
+        const auto r = __builtin_amdgcn_permlane32_swap(__float_as_int(x), __float_as_int(x), false, false);
+        x = __int_as_float(r[0]) + __int_as_float(r[1]);
+    }
+    return x;
+}
+
+// Sums of four values per lane (S0..S3, e.g. the partial sums of four matrix rows) over the LPR
+// lanes of a group (LPR = 16, 32 or 64 consecutive lanes), at a third of the exchanges four
+// separate all-reduces would take: the first two levels halve the number of values a lane
+// carries instead of doubling the copies.  Every lane returns the complete sum of value number
+// 2 * (lane & 1) + ((lane >> 1) & 1).  Lanes of one group that own the same value may differ in
+// the last bit (they add in different orders); each caller lets one lane per value publish it.
+template <int LPR>
+__device__ __forceinline__ float reduce4_over_lanes(float S0, float S1, float S2, float S3, int lane) {
+    static_assert(LPR == 16 || LPR == 32 || LPR == 64, "a row spans 16, 32 or 64 lanes");
+    const bool b0 = (lane & 1) != 0, b1 = (lane & 2) != 0;
+    const float keepA = (b0 ? S2 : S0) + dpp<kDppQuadXor1>(b0 ? S0 : S2);
+    const float keepB = (b0 ? S3 : S1) + dpp<kDppQuadXor1>(b0 ? S1 : S3);
+    float x = (b1 ? keepB : keepA) + dpp<kDppQuadXor2>(b1 ? keepA : keepB);
+    x += dpp<kDppRowRor4>(x);
+    x += dpp<kDppRowRor8>(x);
+    if (LPR >= 32) {
+        const auto r = __builtin_amdgcn_permlane16_swap(__float_as_int(x), __float_as_int(x), false, false);
+        x = __int_as_float(r[0]) + __int_as_float(r[1]);
+    }
+    if (LPR >= 64) {
         const auto r = __builtin_amdgcn_permlane32_swap(__float_as_int(x), __float_as_int(x), false, false);
         x = __int_as_float(r[0]) + __int_as_float(r[1]);
     }

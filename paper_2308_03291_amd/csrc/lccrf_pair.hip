@@ -21,6 +21,7 @@
 // a bounded number of polls marks the sequence as failed and stops; the one-workgroup exact
 // kernel then recomputes the failed sequences.  Correctness therefore never depends on both
 // partners being resident at the same time, only the speed does.
+#include "lccrf_chain_args.h"
 #include "lccrf_device.h"
 #include "lccrf_launch.h"
 
@@ -162,7 +163,7 @@ __global__ __launch_bounds__(kPairThreads) void pair_marginal_kernel(PairArgs a)
         if (tid == 0) *failed = 1;
         return;
     }
-    const int h = L / 2;
+    const int h = meeting_point(0, L - 1);
     const TIN* phib = static_cast<const TIN*>(a.phi) + (size_t)b * N * TT;
     unsigned long long* mine = a.mail + ((size_t)chain * 2 + p) * 2 * kPairMailWords;
     const unsigned long long* theirs = a.mail + ((size_t)chain * 2 + (1 - p)) * 2 * kPairMailWords;

@@ -234,7 +234,7 @@ __global__ __launch_bounds__(64) void wave_half_kernel(ChainArgs a) {
     if (sp.empty) return;
     const int b = sp.b, N = a.N, T = a.T;
     const int p0 = sp.p0, e = sp.e;
-    const int h = p0 + (e - p0 + 1) / 2;
+    const int h = meeting_point(p0, e);
     const size_t TT = (size_t)T * T, vb = (size_t)b * N;
     const TIN* phib = static_cast<const TIN*>(a.phi) + (size_t)b * N * TT;
     const bool exact_only = a.exact_only != 0;
@@ -343,7 +343,7 @@ __global__ __launch_bounds__(64) void wave_marginal_kernel(ChainArgs a) {
     }
     if (sp.empty) return;
     const int p0 = sp.p0, e = sp.e;
-    const int h = p0 + (e - p0 + 1) / 2;
+    const int h = meeting_point(p0, e);
     const TIN* phib = static_cast<const TIN*>(a.phi) + (size_t)b * N * TT;
 
     // log2 Z from the two vectors stored for the meeting position
