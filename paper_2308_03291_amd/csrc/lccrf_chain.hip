@@ -522,6 +522,10 @@ __global__ __launch_bounds__(G::W) void chain_half_kernel(ChainArgs a) {
     const Span sp = make_span(a, blockIdx.x >> 1);
     const int b = sp.b;
     const int N = a.N, T = a.T;
+    if (a.pair_mail && dir == 0) {  // the second pass finds its mailboxes and failure flag clean
+        for (int k = tid; k < a.pair_words; k += G::W) a.pair_mail[(size_t)b * a.pair_words + k] = 0ull;
+        if (tid == 0) a.pair_failed[b] = 0;
+    }
     if (sp.empty) return;
     const int p0 = sp.p0, e = sp.e;
     const int h = meeting_point(p0, e);
@@ -797,8 +801,7 @@ static hipError_t launch_geo(int op, ChainArgs a, hipStream_t st, hipEvent_t bet
     }
     if (pair.mail) {
         // two workgroups per chain, speculative steps only; whatever they flag as failed is redone below
-        e = launch_pair_reset(pair.mail, a.B, pair.failed, st);
-        if (e != hipSuccess) return e;
+        // (the first pass above has cleared the mailboxes and the flags: a.pair_mail)
         e = launch_pair_marginals(pair.dtype, a.phi, a.lengths, a.B, a.N, a.T, a.ua, a.ub, a.Oa, a.Ob, a.logZ, a.mu,
                                   pair.mail, pair.failed, st);
         if (e != hipSuccess) return e;
@@ -846,6 +849,11 @@ hipError_t launch_sequential_sum(int op, int dtype, const void* phi, const int32
     }();
     const bool use_pairs = op == 1 && !exact_only && mail && failed && pair_supported(T) && 4 * B <= cus;
     const PairPlan pair{use_pairs ? mail : nullptr, failed, dtype};
+    if (use_pairs) {
+        a.pair_mail = mail;
+        a.pair_failed = failed;
+        a.pair_words = (int)pair_mail_words(1);
+    }
     const bool aligned = (T % 4) == 0;
     if (dtype == 0)
         return aligned ? launch_T<float, true>(op, a, st, between, pair) : launch_T<float, false>(op, a, st, between, pair);

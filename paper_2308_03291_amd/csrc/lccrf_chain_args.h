@@ -26,6 +26,11 @@ struct ChainArgs {
     const double* OF;  // [B][C] its offset
     const float* Gv;   // [B][C][T] beta at the last position of each chunk, normalised
     const double* OG;  // [B][C]
+    // Scratch of the paired second pass, cleared by the first pass when it is going to be used
+    // (null otherwise): pair_words 8-byte mailbox words and one failure flag per sequence.
+    unsigned long long* pair_mail;
+    int* pair_failed;
+    int pair_words;
 };
 
 // The stretch of positions one pair of workgroups handles: all of a sequence, or one chunk.

@@ -121,6 +121,13 @@ __device__ __forceinline__ void store_tile(float* __restrict__ mat, int T, int c
 // Cross-lane moves on the DPP path (no LDS).  Written with a zero `old` value and bound_ctrl set,
 // the form the compiler can fold into the consuming add or max (v_add_f32_dpp) instead of a copy,
 // a hazard nop and a separate move.
+// A translation unit may define LCCRF_LANE_EXCHANGE_CLASSIC before including this header to get
+// the plain forms instead (a move with its own register and the LDS swizzle at distance 4).
+#ifdef LCCRF_LANE_EXCHANGE_CLASSIC
+constexpr bool kNoMirror = true;
+#else
+constexpr bool kNoMirror = false;
+#endif
 constexpr int kDppQuadXor1 = 0xB1;     // quad_perm [1,0,3,2]
 constexpr int kDppQuadXor2 = 0x4E;     // quad_perm [2,3,0,1]
 constexpr int kDppRowRor4 = 0x124;     // rotate right by 4 within a row of 16 lanes
@@ -128,7 +135,11 @@ constexpr int kDppRowRor8 = 0x128;
 constexpr int kDppHalfMirror = 0x141;  // lane i <-> 7 - i within each group of 8 lanes
 template <int CTRL>
 __device__ __forceinline__ float dpp(float x) {
+#ifdef LCCRF_LANE_EXCHANGE_CLASSIC
+    return __int_as_float(__builtin_amdgcn_update_dpp(__float_as_int(x), __float_as_int(x), CTRL, 0xF, 0xF, false));
+#else
     return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), CTRL, 0xF, 0xF, true));
+#endif
 }
 template <int CTRL>
 __device__ __forceinline__ int dpp_i(int x) { return __builtin_amdgcn_update_dpp(0, x, CTRL, 0xF, 0xF, true); }
@@ -171,7 +182,7 @@ template <int LO, int HI>
 __device__ __forceinline__ float xor_max(float x) {
     if (LO <= 1 && 1 < HI) x = fmaxf(x, dpp<kDppQuadXor1>(x));
     if (LO <= 2 && 2 < HI) x = fmaxf(x, dpp<kDppQuadXor2>(x));
-    if (LO <= 4 && 4 < HI) x = fmaxf(x, LO <= 1 ? dpp<kDppHalfMirror>(x) : lane_xor<4>(x));
+    if (LO <= 4 && 4 < HI) x = fmaxf(x, (LO <= 1 && !kNoMirror) ? dpp<kDppHalfMirror>(x) : lane_xor<4>(x));
     if (LO <= 8 && 8 < HI) x = fmaxf(x, dpp<kDppRowRor8>(x));
     if (LO <= 16 && 16 < HI) {  // both halves of the swapped pair: no select needed for a symmetric op
         const auto r = __builtin_amdgcn_permlane16_swap(__float_as_int(x), __float_as_int(x), false, false);
@@ -187,7 +198,7 @@ template <int LO, int HI>
 __device__ __forceinline__ float xor_sum(float x) {
     if (LO <= 1 && 1 < HI) x += dpp<kDppQuadXor1>(x);
     if (LO <= 2 && 2 < HI) x += dpp<kDppQuadXor2>(x);
-    if (LO <= 4 && 4 < HI) x += LO <= 1 ? dpp<kDppHalfMirror>(x) : lane_xor<4>(x);
+    if (LO <= 4 && 4 < HI) x += (LO <= 1 && !kNoMirror) ? dpp<kDppHalfMirror>(x) : lane_xor<4>(x);
     if (LO <= 8 && 8 < HI) x += dpp<kDppRowRor8>(x);
     if (LO <= 16 && 16 < HI) {
         const auto r = __builtin_amdgcn_permlane16_swap(__float_as_int(x), __float_as_int(x), false, false);

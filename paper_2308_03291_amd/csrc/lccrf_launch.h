@@ -22,7 +22,6 @@ hipError_t launch_sequential_sum(int op, int dtype, const void* phi, const int32
 // Paired second pass (two workgroups per chain; lccrf_pair.hip).
 size_t pair_mail_words(int B);
 bool pair_supported(int T);
-hipError_t launch_pair_reset(unsigned long long* mail, int B, int* failed, hipStream_t st);
 hipError_t launch_pair_marginals(int dtype, const void* phi, const int32_t* lengths, int B, int N, int T,
                                  const float* ua, const float* ub, const double* Oa, const double* Ob,
                                  float* logZ, float* mu, unsigned long long* mail, int* failed, hipStream_t st);
