@@ -38,7 +38,7 @@ inline SumWorkspace sum_workspace(size_t B, size_t N, size_t T) {
     return w;
 }
 struct MaxWorkspace {
-    size_t bp;
+    size_t bp, mid;
     size_t Mx, K, pin;  // chunked scan (T <= 16 only, else empty)
     size_t total;
 };
@@ -47,6 +47,7 @@ inline MaxWorkspace max_workspace(size_t B, size_t N, size_t T) {
     size_t off = 0;
     w.bp = off; off += round_up(B * N * T);
     const size_t BC = lccrf::scan_supported((int)T) ? B * ((N + g_scan_chunk - 1) / g_scan_chunk) : 0;
+    w.mid = off; off += round_up((BC > B ? BC : B) * 2 * T * sizeof(double));
     w.Mx = off; off += round_up(BC * 256 * sizeof(double));
     w.K = off; off += round_up(BC * 16);
     w.pin = off; off += round_up(BC * sizeof(int32_t));
@@ -170,14 +171,16 @@ int lccrf_argmax_algo(const void* phi, lccrf_dtype dt, const int32_t* lengths, i
     char* base = static_cast<char*>(workspace);
     hipStream_t st = static_cast<hipStream_t>(stream);
     uint8_t* bp = reinterpret_cast<uint8_t*>(base + w.bp);
+    double* mid = reinterpret_cast<double*>(base + w.mid);
     hipError_t e;
     if (algo == LCCRF_ALGO_SCAN || (algo == LCCRF_ALGO_AUTO && scan_pays(B, N, T))) {
         int32_t* pin = reinterpret_cast<int32_t*>(base + w.pin);
         e = lccrf::launch_scan_pins(dt, phi, lengths, B, N, T, g_scan_chunk, reinterpret_cast<double*>(base + w.Mx),
                                     reinterpret_cast<uint8_t*>(base + w.K), pin, best_score, st);
-        if (e == hipSuccess) e = lccrf::launch_chunked_max(dt, phi, lengths, B, N, T, bp, tags, g_scan_chunk, pin, st);
+        if (e == hipSuccess)
+            e = lccrf::launch_chunked_max(dt, phi, lengths, B, N, T, bp, mid, tags, g_scan_chunk, pin, st);
     } else {
-        e = lccrf::launch_sequential_max(dt, phi, lengths, B, N, T, bp, best_score, tags, st);
+        e = lccrf::launch_sequential_max(dt, phi, lengths, B, N, T, bp, mid, best_score, tags, st);
     }
     return e == hipSuccess ? LCCRF_OK : LCCRF_ELAUNCH;
 }

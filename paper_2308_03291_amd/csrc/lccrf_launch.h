@@ -40,16 +40,19 @@ hipError_t launch_chunked_marginals(int dtype, const void* phi, const int32_t* l
                                     const float* Fv, const double* OF, const float* Gv, const double* OG,
                                     hipStream_t st, hipEvent_t between, bool exact_only);
 
-// Max-plus chain with back-pointers and back-trace.  bp: [B][N][T] bytes of scratch.
+// Max-plus chains (two per sequence, meeting in the middle) and the trace.  bp: [B][N][T] bytes,
+// mid: viterbi_mid_doubles(B, 1, T) doubles of scratch.
+size_t viterbi_mid_doubles(int B, int C, int T);
 hipError_t launch_sequential_max(int dtype, const void* phi, const int32_t* lengths, int B, int N, int T,
-                                 uint8_t* bp, float* best_score, int32_t* tags, hipStream_t st);
+                                 uint8_t* bp, double* mid, float* best_score, int32_t* tags, hipStream_t st);
 
 // Max-plus chunked scan (lccrf_scan.hip): the best score and the tag of the best path at the last
 // position of every chunk (pin: [B][C] ints).  Mx: [B][C][256] doubles, K: [B][C][16] bytes of scratch.
 hipError_t launch_scan_pins(int dtype, const void* phi, const int32_t* lengths, int B, int N, int T, int chunk,
                             double* Mx, uint8_t* K, int32_t* pin, float* best_score, hipStream_t st);
-// Best path inside every chunk between those pinned tags (lccrf_viterbi.hip).
+// Best path inside every chunk between those pinned tags (lccrf_viterbi.hip);
+// mid: viterbi_mid_doubles(B, C, T) doubles of scratch.
 hipError_t launch_chunked_max(int dtype, const void* phi, const int32_t* lengths, int B, int N, int T, uint8_t* bp,
-                              int32_t* tags, int chunk, const int32_t* pin, hipStream_t st);
+                              double* mid, int32_t* tags, int chunk, const int32_t* pin, hipStream_t st);
 
 }  // namespace lccrf

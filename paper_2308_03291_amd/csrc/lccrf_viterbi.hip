@@ -1,31 +1,35 @@
-// Max-plus (Viterbi) chain for the linear-chain CRF: the recursion of the forward
+// Max-plus (Viterbi) chains for the linear-chain CRF: the recursion of the forward
 // algorithm with (max, +) in place of (logsumexp, +), as the paper's section "Computing
-// Most Probable Structure" prescribes, followed by the back-trace that reads off the path.
+// Most Probable Structure" prescribes, followed by the trace that reads off the path.
 //
-// delta is carried in double precision and never rescaled: max-plus needs only additions and
-// comparisons, both run at the full vector rate in fp64 on this chip, and every candidate
-// delta_{i-1}(s) + phi_i(s,t) is then one correctly rounded fp64 addition of exactly
-// representable inputs, whichever thread forms it.  Ties go to the smaller previous tag.
+// Like the sum-product chains, every sequence (or every chunk of the scan) is served by two
+// chains that meet in the middle, at half the serial depth:
+//
+//   forward  workgroup: delta_i(t) = max_s delta_{i-1}(s) + phi_i(s,t) for i <= h, with the
+//       back-pointer bp_i(t) = the best s;
+//   backward workgroup: eps_{i-1}(s) = max_t phi_i(s,t) + eps_i(t) for i > h, with the
+//       forward pointer fp_i(s) = the best t (stored in the same table, rows i > h);
+//   trace (viterbi_trace_kernel): y_h = argmax_t delta_h(t) + eps_h(t), then y_{i-1} = bp_i(y_i)
+//       down to the first position and y_i = fp_i(y_{i-1}) up to the last, by two threads.
+//
+// Scores are carried in double precision and never rescaled: max-plus needs only additions and
+// comparisons, both at the full vector rate in fp64 on this chip, and every candidate is then one
+// correctly rounded fp64 addition of exactly representable inputs, whichever thread forms it.
+// Ties go to the smaller tag.
+#include "lccrf_chain_args.h"
 #include "lccrf_device.h"
 #include "lccrf_launch.h"
 
 namespace lccrf {
 
 constexpr int kNoArg = 0x7fffffff;
-constexpr int kTraceBytes = 16384;  // LDS window of back-pointers walked by the back-trace
+constexpr int kTraceBytes = 16384;  // LDS window of pointers walked by each trace
 
 template <typename G>
 struct VitSmem {
-    union {
-        struct {
-            double pv[G::WAVES][G::TCAP];  // per-wave best candidate per column
-            int pi[G::WAVES][G::TCAP];     // and its previous tag
-        } f;
-        uint8_t window[kTraceBytes];
-    } u;
+    double pv[G::WAVES][G::TCAP];  // per-wave best candidate per column (forward merge)
+    int pi[G::WAVES][G::TCAP];     // and its previous tag
     double dvec[2][G::TCAP];
-    double best;
-    int last;
 };
 
 __device__ __forceinline__ void take_better(double& v, int& a, double pv, int pa) {
@@ -36,57 +40,73 @@ struct VitArgs {
     const void* phi;
     const int32_t* lengths;
     int B, N, T;
-    uint8_t* bp;  // [B][N][T]
+    uint8_t* bp;   // [B][N][T] back-pointers (rows <= meeting point) and forward pointers (rows above it)
+    double* mid;   // [B][C][2][T] delta and eps at the meeting point
     float* best_score;
     int32_t* tags;
-    // Chunked schedule (chunk > 0): workgroup v serves chunk c = v % C of sequence v / C, the tag
-    // positions [c chunk, (c+1) chunk), as a chain of its own that starts one position earlier in
+    // Chunked schedule (chunk > 0): workgroup pair v serves chunk c = v % C of sequence v / C, the
+    // tag positions [c chunk, (c+1) chunk), as a chain of its own that starts one position earlier in
     // the tag pin[b][c-1] and must end in the tag pin[b][c] (both chosen by the max-plus scan,
     // lccrf_scan.hip); the best score is the scan's and is not written here.
     int chunk, C;
     const int32_t* pin;  // [B][C] tag at the last position of each chunk
 };
 
+// The stretch of positions one pair of workgroups handles.
+struct VitSpan {
+    int b, c, L;
+    int t0, t1;  // tag positions [t0, t1) whose tags this span writes (before the cut at L)
+    int p0, e;   // first and last position of the chain
+    bool empty;
+};
+__device__ __forceinline__ VitSpan vit_span(const VitArgs& a, int v) {
+    VitSpan s;
+    const bool chunked = a.chunk > 0;
+    s.b = chunked ? v / a.C : v;
+    s.c = chunked ? v % a.C : 0;
+    s.L = clamp_length(a.lengths, s.b, a.N);
+    s.t0 = chunked ? s.c * a.chunk : 0;
+    s.t1 = chunked ? (s.t0 + a.chunk < a.N ? s.t0 + a.chunk : a.N) : a.N;
+    s.empty = s.t0 >= s.L;
+    s.p0 = s.t0 > 0 ? s.t0 - 1 : 0;
+    s.e = (s.t1 < s.L ? s.t1 : s.L) - 1;
+    return s;
+}
+
 template <typename G, typename TIN, bool ALIGNED>
-__global__ __launch_bounds__(G::W) void viterbi_kernel(VitArgs a) {
+__global__ __launch_bounds__(G::W) void viterbi_half_kernel(VitArgs a) {
     __shared__ VitSmem<G> sm;
     constexpr int ITEMS = G::ITEMS;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const bool chunked = a.chunk > 0;
-    const int b = chunked ? blockIdx.x / a.C : blockIdx.x;
-    const int c = chunked ? blockIdx.x % a.C : 0;
-    const int N = a.N, T = a.T;
-    const int L = clamp_length(a.lengths, b, N);
-    int32_t* tags = a.tags + (size_t)b * N;
-    // this workgroup's stretch of tag positions [t0, t1), cut at the length: first position p0
-    // (carries the start vector) and last position e of its chain
-    const int t0 = chunked ? c * a.chunk : 0;
-    const int t1 = chunked ? (t0 + a.chunk < N ? t0 + a.chunk : N) : N;
-    for (int i = (L > t0 ? L : t0) + tid; i < t1; i += G::W) tags[i] = -1;
-    if (L == 0) {
-        if (!chunked && tid == 0 && a.best_score) a.best_score[b] = 0.f;
-        return;
-    }
-    if (t0 >= L) return;
-    const int p0 = t0 > 0 ? t0 - 1 : 0;
-    const int e = (t1 < L ? t1 : L) - 1;
+    const int dir = blockIdx.x & 1;
+    const VitSpan sp = vit_span(a, blockIdx.x >> 1);
+    if (sp.empty) return;
+    const int b = sp.b, N = a.N, T = a.T;
+    const int p0 = sp.p0, e = sp.e, h = meeting_point(p0, e);
     const int c4 = 4 * (tid % G::LPR), r0 = tid / G::LPR;
     const size_t TT = (size_t)T * T;
     const TIN* phib = static_cast<const TIN*>(a.phi) + (size_t)b * N * TT;
     uint8_t* bpb = a.bp + (size_t)b * N * T;
+    double* mid = a.mid + (((size_t)b * a.C + sp.c) * 2 + dir) * T;
     const double ninf = -__builtin_huge_val();
 
     for (int k = tid; k < 2 * G::TCAP; k += G::W) (&sm.dvec[0][0])[k] = ninf;
     __syncthreads();
     if (tid < T) {
-        if (t0 == 0) sm.dvec[0][tid] = (double)Elem<TIN>::get(phib + tid);
-        else sm.dvec[0][tid] = (tid == a.pin[(size_t)b * a.C + c - 1]) ? 0.0 : ninf;
+        if (dir == 0) {
+            if (sp.t0 == 0) sm.dvec[0][tid] = (double)Elem<TIN>::get(phib + tid);
+            else sm.dvec[0][tid] = (tid == a.pin[(size_t)b * a.C + sp.c - 1]) ? 0.0 : ninf;
+        } else {
+            // a whole sequence may end in any tag; a chunk must end in its pinned tag
+            sm.dvec[0][tid] = (a.chunk <= 0 || tid == a.pin[(size_t)b * a.C + sp.c]) ? 0.0 : ninf;
+        }
     }
     __syncthreads();
 
     int buf = 0;
     float A[ITEMS][4], Bq[ITEMS][4];
-    auto step = [&](int i, float (&v)[ITEMS][4]) {
+    // forward: column maxima over rows, merged across waves through LDS
+    auto fwd_step = [&](int i, float (&v)[ITEMS][4]) {
         mask_tile<G>(v, T, c4, r0);
         double best[4] = {ninf, ninf, ninf, ninf};
         int arg[4] = {kNoArg, kNoArg, kNoArg, kNoArg};
@@ -112,8 +132,8 @@ __global__ __launch_bounds__(G::W) void viterbi_kernel(VitArgs a) {
         if (lane < G::LPR) {
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
-                sm.u.f.pv[wave][c4 + j] = best[j];
-                sm.u.f.pi[wave][c4 + j] = arg[j];
+                sm.pv[wave][c4 + j] = best[j];
+                sm.pi[wave][c4 + j] = arg[j];
             }
         }
         __syncthreads();
@@ -121,32 +141,89 @@ __global__ __launch_bounds__(G::W) void viterbi_kernel(VitArgs a) {
             double bv = ninf;
             int ba = kNoArg;
 #pragma unroll
-            for (int w = 0; w < G::WAVES; ++w) take_better(bv, ba, sm.u.f.pv[w][tid], sm.u.f.pi[w][tid]);
+            for (int w = 0; w < G::WAVES; ++w) take_better(bv, ba, sm.pv[w][tid], sm.pi[w][tid]);
             sm.dvec[buf ^ 1][tid] = bv;
             if (tid < T) bpb[(size_t)i * T + tid] = (uint8_t)(ba == kNoArg ? 0 : ba);
         }
         __syncthreads();
         buf ^= 1;
     };
-    int i = p0 + 1;
-    if (i <= e) load_tile<G, TIN, ALIGNED>(phib + (size_t)i * TT, T, c4, r0, A);
-    while (i <= e) {
-        if (i + 1 <= e) load_tile<G, TIN, ALIGNED>(phib + (size_t)(i + 1) * TT, T, c4, r0, Bq);
-        step(i, A);
-        if (++i > e) break;
-        if (i + 1 <= e) load_tile<G, TIN, ALIGNED>(phib + (size_t)(i + 1) * TT, T, c4, r0, A);
-        step(i, Bq);
-        ++i;
-    }
+    // backward: row maxima over columns, inside the wave
+    auto bwd_step = [&](int i, float (&v)[ITEMS][4]) {
+        mask_tile<G>(v, T, c4, r0);
+        double ek[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) ek[j] = (c4 + j < T) ? sm.dvec[buf][c4 + j] : ninf;
+#pragma unroll
+        for (int k = 0; k < ITEMS; ++k) {
+            double bv = ninf;
+            int ba = kNoArg;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {  // ascending columns: the first maximum wins
+                const double val = (double)v[k][j] + ek[j];
+                if (val > bv) { bv = val; ba = c4 + j; }
+            }
+#pragma unroll
+            for (int off = 1; off < G::LPR; off <<= 1) {
+                const double pv = __shfl_xor(bv, off, 64);
+                const int pa = __shfl_xor(ba, off, 64);
+                take_better(bv, ba, pv, pa);
+            }
+            const int s = r0 + k * G::RPP;
+            if (c4 == 0 && s < T) {
+                sm.dvec[buf ^ 1][s] = bv;
+                bpb[(size_t)i * T + s] = (uint8_t)(ba == kNoArg ? 0 : ba);
+            }
+        }
+        __syncthreads();
+        buf ^= 1;
+    };
+    auto run = [&](int first, int last, int step_dir, auto step) {  // two-deep software pipeline over the tiles
+        int i = first;
+        const int n = (last - first) * step_dir + 1;
+        if (n <= 0) return;
+        int left = n;
+        load_tile<G, TIN, ALIGNED>(phib + (size_t)i * TT, T, c4, r0, A);
+        while (left > 0) {
+            if (left > 1) load_tile<G, TIN, ALIGNED>(phib + (size_t)(i + step_dir) * TT, T, c4, r0, Bq);
+            step(i, A);
+            i += step_dir;
+            if (--left == 0) break;
+            if (left > 1) load_tile<G, TIN, ALIGNED>(phib + (size_t)(i + step_dir) * TT, T, c4, r0, A);
+            step(i, Bq);
+            i += step_dir;
+            --left;
+        }
+    };
+    if (dir == 0) run(p0 + 1, h, +1, fwd_step);
+    else run(e, h + 1, -1, bwd_step);
+    if (tid < T) mid[tid] = sm.dvec[buf][tid];
+}
 
-    if (chunked) {
-        if (tid == 0) sm.last = a.pin[(size_t)b * a.C + c];
-    } else if (wave == 0) {
-        // best final tag: first maximum of delta_{L-1}
+// Joins the two chains at the meeting point and reads off the path.
+__global__ __launch_bounds__(128) void viterbi_trace_kernel(VitArgs a) {
+    __shared__ uint8_t window[2][kTraceBytes];
+    __shared__ int start;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const VitSpan sp = vit_span(a, blockIdx.x);
+    const int b = sp.b, N = a.N, T = a.T, L = sp.L;
+    int32_t* tags = a.tags + (size_t)b * N;
+    for (int i = (L > sp.t0 ? L : sp.t0) + tid; i < sp.t1; i += 128) tags[i] = -1;
+    if (L == 0) {
+        if (a.chunk <= 0 && tid == 0 && a.best_score) a.best_score[b] = 0.f;
+        return;
+    }
+    if (sp.empty) return;
+    const int p0 = sp.p0, e = sp.e, h = meeting_point(p0, e);
+    const uint8_t* bpb = a.bp + (size_t)b * N * T;
+    const double* mid = a.mid + ((size_t)b * a.C + sp.c) * 2 * T;
+    const double ninf = -__builtin_huge_val();
+
+    if (wave == 0) {  // best tag at the meeting point: first maximum of delta_h + eps_h
         double bv = ninf;
         int ba = kNoArg;
         for (int t = lane; t < T; t += 64) {
-            const double val = sm.dvec[buf][t];
+            const double val = mid[t] + mid[T + t];
             if (val > bv) { bv = val; ba = t; }
         }
 #pragma unroll
@@ -156,41 +233,56 @@ __global__ __launch_bounds__(G::W) void viterbi_kernel(VitArgs a) {
             take_better(bv, ba, pv, pa);
         }
         if (lane == 0) {
-            sm.best = bv;
-            sm.last = (ba == kNoArg) ? 0 : ba;
-            if (a.best_score) a.best_score[b] = (float)bv;
+            start = (ba == kNoArg) ? 0 : ba;
+            if (a.chunk <= 0 && a.best_score) a.best_score[b] = (float)bv;
         }
     }
-    __threadfence();  // back-pointers written above are read back below by other threads
     __syncthreads();
-
-    // back-trace: y_{i-1} = bp_i(y_i), walked through an LDS window of back-pointers
-    // (a chunk leaves the tag of its entry position p0 to the chunk that ends there)
     const int rows_per_window = kTraceBytes / T;
-    int y = sm.last;
-    if (tid == 0) tags[e] = y;
-    const int stop = t0 == 0 ? 1 : t0 + 1;  // rows [stop, hi) still to walk; row r yields tag r - 1
-    int hi = e + 1;
-    while (hi > stop) {
-        const int lo = (hi - rows_per_window > stop) ? hi - rows_per_window : stop;
-        const int nbytes = (hi - lo) * T;
-        const uint8_t* src = bpb + (size_t)lo * T;
-        for (int k = tid; k < nbytes; k += G::W) sm.u.window[k] = src[k];
+    int y = start;
+    if (tid == 0) tags[h] = y;
+    // wave 0 walks down: row r yields the tag of position r - 1 (a chunk leaves the tag of its entry
+    // position p0 to the chunk that ends there); wave 1 walks up: row r yields the tag of position r
+    const int stop = sp.t0 == 0 ? 1 : sp.t0 + 1;
+    int hi = h + 1;   // rows [stop, hi) still to walk down
+    int lo = h + 1;   // rows [lo, e] still to walk up
+    while (hi > stop || lo <= e) {  // both waves make the same number of trips: barriers stay matched
+        const int dlo = (hi - rows_per_window > stop) ? hi - rows_per_window : stop;
+        const int uhi = (lo + rows_per_window - 1 < e) ? lo + rows_per_window - 1 : e;
+        if (wave == 0) {
+            const int nbytes = hi > stop ? (hi - dlo) * T : 0;
+            const uint8_t* src = bpb + (size_t)dlo * T;
+            for (int k = lane; k < nbytes; k += 64) window[0][k] = src[k];
+        } else {
+            const int nbytes = lo <= e ? (uhi - lo + 1) * T : 0;
+            const uint8_t* src = bpb + (size_t)lo * T;
+            for (int k = lane; k < nbytes; k += 64) window[1][k] = src[k];
+        }
         __syncthreads();
-        if (tid == 0) {
-            for (int r = hi - 1; r >= lo; --r) {
-                y = sm.u.window[(r - lo) * T + y];
+        if (tid == 0 && hi > stop) {
+            for (int r = hi - 1; r >= dlo; --r) {
+                y = window[0][(r - dlo) * T + y];
                 tags[r - 1] = y;
             }
         }
+        if (tid == 64 && lo <= e) {
+            for (int r = lo; r <= uhi; ++r) {
+                y = window[1][(r - lo) * T + y];
+                tags[r] = y;
+            }
+        }
         __syncthreads();
-        hi = lo;
+        if (hi > stop) hi = dlo;
+        if (lo <= e) lo = uhi + 1;
     }
 }
 
 template <typename G, typename TIN, bool ALIGNED>
 static hipError_t launch_geo(const VitArgs& a, hipStream_t st) {
-    hipLaunchKernelGGL((viterbi_kernel<G, TIN, ALIGNED>), dim3(a.B * a.C), dim3(G::W), 0, st, a);
+    hipLaunchKernelGGL((viterbi_half_kernel<G, TIN, ALIGNED>), dim3(2 * a.B * a.C), dim3(G::W), 0, st, a);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(viterbi_trace_kernel, dim3(a.B * a.C), dim3(128), 0, st, a);
     return hipGetLastError();
 }
 
@@ -206,21 +298,23 @@ static hipError_t launch_T(const VitArgs& a, hipStream_t st) {
     return launch_geo<Geo<64, 16, 16>, TIN, ALIGNED>(a, st);
 }
 
-hipError_t launch_sequential_max(int dtype, const void* phi, const int32_t* lengths, int B, int N, int T,
-                                 uint8_t* bp, float* best_score, int32_t* tags, hipStream_t st) {
-    VitArgs a{phi, lengths, B, N, T, bp, best_score, tags, 0, 1, nullptr};
-    const bool aligned = (T % 4) == 0;
+static hipError_t launch_any(int dtype, const VitArgs& a, hipStream_t st) {
+    const bool aligned = (a.T % 4) == 0;
     if (dtype == 0) return aligned ? launch_T<float, true>(a, st) : launch_T<float, false>(a, st);
     return aligned ? launch_T<uint16_t, true>(a, st) : launch_T<uint16_t, false>(a, st);
 }
 
+size_t viterbi_mid_doubles(int B, int C, int T) { return (size_t)B * C * 2 * T; }
+
+hipError_t launch_sequential_max(int dtype, const void* phi, const int32_t* lengths, int B, int N, int T,
+                                 uint8_t* bp, double* mid, float* best_score, int32_t* tags, hipStream_t st) {
+    return launch_any(dtype, VitArgs{phi, lengths, B, N, T, bp, mid, best_score, tags, 0, 1, nullptr}, st);
+}
+
 // Best path inside every chunk between the tags the max-plus scan has pinned at the chunk ends.
 hipError_t launch_chunked_max(int dtype, const void* phi, const int32_t* lengths, int B, int N, int T, uint8_t* bp,
-                              int32_t* tags, int chunk, const int32_t* pin, hipStream_t st) {
-    VitArgs a{phi, lengths, B, N, T, bp, nullptr, tags, chunk, (N + chunk - 1) / chunk, pin};
-    const bool aligned = (T % 4) == 0;
-    if (dtype == 0) return aligned ? launch_T<float, true>(a, st) : launch_T<float, false>(a, st);
-    return aligned ? launch_T<uint16_t, true>(a, st) : launch_T<uint16_t, false>(a, st);
+                              double* mid, int32_t* tags, int chunk, const int32_t* pin, hipStream_t st) {
+    return launch_any(dtype, VitArgs{phi, lengths, B, N, T, bp, mid, nullptr, tags, chunk, (N + chunk - 1) / chunk, pin}, st);
 }
 
 }  // namespace lccrf
