@@ -382,8 +382,6 @@ __device__ __forceinline__ void bwd_advance(ChainSmem<G>& sm, int& buf, int& nst
 // Lane l of wave w holds rows (l % 32) + 32 k, k < 4, of columns 8 w + 4 (l / 32) + j, j < 4.
 template <typename G, bool ALIGNED, int PF>
 constexpr bool half_turns() { return G::LPR == 32 && G::WAVES == 16 && G::ITEMS == 4 && ALIGNED && PF == 4; }
-constexpr int kTurnStride = 132;  // floats per LDS row: 128 + 4 keeps 16-byte accesses conflict free
-constexpr int kTurnFloats = 2 * 128 * kTurnStride;
 
 template <typename G, typename TIN, int PF>
 __device__ __forceinline__ void forward_half_turned(ChainSmem<G>& sm, float* __restrict__ tiles, const ChainArgs& a,

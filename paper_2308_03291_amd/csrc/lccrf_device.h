@@ -237,6 +237,61 @@ __device__ __forceinline__ float reduce4_over_lanes(float S0, float S1, float S2
     return x;
 }
 
+// LDS layout of a tile that is written row by row and read back column-block by column-block
+// (forward chains at 64 < T <= 128): two buffers of 128 rows.
+constexpr int kTurnStride = 132;  // floats per LDS row: 128 + 4 keeps 16-byte accesses conflict free
+constexpr int kTurnFloats = 2 * 128 * kTurnStride;
+
+// A candidate of a max-plus step: its score and the tag it comes from.  Ties go to the smaller tag,
+// which makes `better` commutative and associative: any reduction order gives the same winner.
+struct Best {
+    double v;
+    int a;
+};
+__device__ __forceinline__ Best better(Best x, Best y) {
+    const bool take_y = y.v > x.v || (y.v == x.v && y.a < x.a);
+    return take_y ? y : x;
+}
+template <int CTRL>
+__device__ __forceinline__ Best dpp_best(Best x) {
+    const long long b = __double_as_longlong(x.v);
+    const int lo = dpp_i<CTRL>((int)(b & 0xffffffffll)), hi = dpp_i<CTRL>((int)(b >> 32));
+    return Best{__longlong_as_double(((long long)hi << 32) | (unsigned int)lo), dpp_i<CTRL>(x.a)};
+}
+// The better of this lane's candidate and that of the lane 16 (W = 16) or 32 (W = 32) away.
+template <int W>
+__device__ __forceinline__ Best swap_best(Best x) {
+    const long long b = __double_as_longlong(x.v);
+    const int lo = (int)(b & 0xffffffffll), hi = (int)(b >> 32);
+    if (W == 16) {
+        const auto rl = __builtin_amdgcn_permlane16_swap(lo, lo, false, false);
+        const auto rh = __builtin_amdgcn_permlane16_swap(hi, hi, false, false);
+        const auto ra = __builtin_amdgcn_permlane16_swap(x.a, x.a, false, false);
+        return better(Best{__longlong_as_double(((long long)(int)rh[0] << 32) | (unsigned int)rl[0]), (int)ra[0]},
+                      Best{__longlong_as_double(((long long)(int)rh[1] << 32) | (unsigned int)rl[1]), (int)ra[1]});
+    }
+    const auto rl = __builtin_amdgcn_permlane32_swap(lo, lo, false, false);
+    const auto rh = __builtin_amdgcn_permlane32_swap(hi, hi, false, false);
+    const auto ra = __builtin_amdgcn_permlane32_swap(x.a, x.a, false, false);
+    return better(Best{__longlong_as_double(((long long)(int)rh[0] << 32) | (unsigned int)rl[0]), (int)ra[0]},
+                  Best{__longlong_as_double(((long long)(int)rh[1] << 32) | (unsigned int)rl[1]), (int)ra[1]});
+}
+// reduce4_over_lanes for candidates: the best of b0..b3 (four rows or columns per lane) over the
+// LPR lanes of a group; every lane returns the winner of number 2 * (lane & 1) + ((lane >> 1) & 1).
+template <int LPR>
+__device__ __forceinline__ Best reduce4_best_over_lanes(Best b0, Best b1, Best b2, Best b3, int lane) {
+    static_assert(LPR == 16 || LPR == 32 || LPR == 64, "a group spans 16, 32 or 64 lanes");
+    const bool o0 = (lane & 1) != 0, o1 = (lane & 2) != 0;
+    const Best keepA = better(o0 ? b2 : b0, dpp_best<kDppQuadXor1>(o0 ? b0 : b2));
+    const Best keepB = better(o0 ? b3 : b1, dpp_best<kDppQuadXor1>(o0 ? b1 : b3));
+    Best x = better(o1 ? keepB : keepA, dpp_best<kDppQuadXor2>(o1 ? keepA : keepB));
+    x = better(x, dpp_best<kDppRowRor4>(x));
+    x = better(x, dpp_best<kDppRowRor8>(x));
+    if (LPR >= 32) x = swap_best<16>(x);
+    if (LPR >= 64) x = swap_best<32>(x);
+    return x;
+}
+
 // Walks positions first, first+dir, ..., last (dir = +1 or -1) with a ring of PF tiles:
 // `load(i, slot)` issues the loads of position i into ring slot `slot`; `step(i, slot)`
 // consumes the slot, which is refilled with the tile PF positions ahead right after.

@@ -25,10 +25,20 @@ namespace lccrf {
 constexpr int kNoArg = 0x7fffffff;
 constexpr int kTraceBytes = 16384;  // LDS window of pointers walked by each trace
 
-template <typename G>
+// Forward chains at 64 < T <= 128 (T % 4 == 0) turn their tiles through LDS like the sum-product
+// first pass does (lccrf_chain.hip): a wave then owns 8 complete columns and the maximum over
+// rows never leaves it, so the per-wave candidates below are not needed.
+template <typename G, bool ALIGNED>
+constexpr bool vit_turns() { return G::LPR == 32 && G::WAVES == 16 && G::ITEMS == 4 && ALIGNED; }
+
+template <typename G, bool TURNED>
 struct VitSmem {
     double pv[G::WAVES][G::TCAP];  // per-wave best candidate per column (forward merge)
     int pi[G::WAVES][G::TCAP];     // and its previous tag
+    double dvec[2][G::TCAP];
+};
+template <typename G>
+struct VitSmem<G, true> {
     double dvec[2][G::TCAP];
 };
 
@@ -75,7 +85,8 @@ __device__ __forceinline__ VitSpan vit_span(const VitArgs& a, int v) {
 
 template <typename G, typename TIN, bool ALIGNED>
 __global__ __launch_bounds__(G::W) void viterbi_half_kernel(VitArgs a) {
-    __shared__ VitSmem<G> sm;
+    constexpr bool TURNED = vit_turns<G, ALIGNED>();
+    __shared__ VitSmem<G, TURNED> sm;
     constexpr int ITEMS = G::ITEMS;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int dir = blockIdx.x & 1;
@@ -107,6 +118,7 @@ __global__ __launch_bounds__(G::W) void viterbi_half_kernel(VitArgs a) {
     float A[ITEMS][4], Bq[ITEMS][4];
     // forward: column maxima over rows, merged across waves through LDS
     auto fwd_step = [&](int i, float (&v)[ITEMS][4]) {
+      if constexpr (!TURNED) {
         mask_tile<G>(v, T, c4, r0);
         double best[4] = {ninf, ninf, ninf, ninf};
         int arg[4] = {kNoArg, kNoArg, kNoArg, kNoArg};
@@ -147,6 +159,7 @@ __global__ __launch_bounds__(G::W) void viterbi_half_kernel(VitArgs a) {
         }
         __syncthreads();
         buf ^= 1;
+      }
     };
     // backward: row maxima over columns, inside the wave
     auto bwd_step = [&](int i, float (&v)[ITEMS][4]) {
@@ -154,6 +167,29 @@ __global__ __launch_bounds__(G::W) void viterbi_half_kernel(VitArgs a) {
         double ek[4];
 #pragma unroll
         for (int j = 0; j < 4; ++j) ek[j] = (c4 + j < T) ? sm.dvec[buf][c4 + j] : ninf;
+        if constexpr (ITEMS % 4 == 0 && G::LPR >= 16) {
+            // four rows at a time: each lane ends up with the winner of one of them
+            const int kk = 2 * (lane & 1) + ((lane >> 1) & 1);
+#pragma unroll
+            for (int k0 = 0; k0 < ITEMS; k0 += 4) {
+                Best c[4];
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    c[q] = Best{ninf, kNoArg};
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {  // ascending columns: the first maximum wins
+                        const double val = (double)v[k0 + q][j] + ek[j];
+                        if (val > c[q].v) c[q] = Best{val, c4 + j};
+                    }
+                }
+                const Best w = reduce4_best_over_lanes<G::LPR>(c[0], c[1], c[2], c[3], lane);
+                const int s = r0 + (k0 + kk) * G::RPP;
+                if ((tid % G::LPR) < 4 && s < T) {
+                    sm.dvec[buf ^ 1][s] = w.v;
+                    bpb[(size_t)i * T + s] = (uint8_t)(w.a == kNoArg ? 0 : w.a);
+                }
+            }
+        } else
 #pragma unroll
         for (int k = 0; k < ITEMS; ++k) {
             double bv = ninf;
@@ -195,8 +231,72 @@ __global__ __launch_bounds__(G::W) void viterbi_half_kernel(VitArgs a) {
             --left;
         }
     };
-    if (dir == 0) run(p0 + 1, h, +1, fwd_step);
-    else run(e, h + 1, -1, bwd_step);
+    if constexpr (TURNED) {
+        if (dir == 0) {
+            extern __shared__ __attribute__((aligned(16))) float turn_tiles[];
+            float* tiles = turn_tiles;
+            constexpr int PF = 4;
+            const int rowl = lane & 31, colw = 8 * wave + 4 * (lane >> 5);
+            const int kk = 2 * (lane & 1) + ((lane >> 1) & 1);
+            const int first = p0 + 1, n = h - p0;
+            if (n > 0) {
+                float ring[PF][4][4];
+                auto load = [&](int i, int slot) { load_tile<G, TIN, true>(phib + (size_t)i * TT, T, c4, r0, ring[slot]); };
+                auto to_lds = [&](int slot, int wb) {
+#pragma unroll
+                    for (int k = 0; k < 4; ++k)
+                        *reinterpret_cast<float4*>(&tiles[(wb * 128 + r0 + 32 * k) * kTurnStride + c4]) =
+                            make_float4(ring[slot][k][0], ring[slot][k][1], ring[slot][k][2], ring[slot][k][3]);
+                };
+#pragma unroll
+                for (int p = 0; p < PF; ++p) load(first + (p < n ? p : n - 1), p);
+                to_lds(0, 0);
+                load(first + (PF < n ? PF : n - 1), 0);
+                __syncthreads();
+                int done = 0;
+                bool running = true;
+                while (running) {
+#pragma unroll
+                    for (int p = 0; p < PF; ++p) {
+                        const int i = first + done;
+                        const int nslot = (p + 1) % PF;
+                        const float* mine = &tiles[((p & 1) * 128 + rowl) * kTurnStride + colw];
+                        Best c[4] = {Best{ninf, kNoArg}, Best{ninf, kNoArg}, Best{ninf, kNoArg}, Best{ninf, kNoArg}};
+#pragma unroll
+                        for (int k = 0; k < 4; ++k) {  // ascending rows: the first maximum wins
+                            const int s = rowl + 32 * k;
+                            const double dk = sm.dvec[buf][s];  // -inf for rows >= T
+                            const float4 q = *reinterpret_cast<const float4*>(mine + 32 * k * kTurnStride);
+                            const double v0 = dk + (double)q.x, v1 = dk + (double)q.y, v2 = dk + (double)q.z, v3 = dk + (double)q.w;
+                            if (v0 > c[0].v) c[0] = Best{v0, s};
+                            if (v1 > c[1].v) c[1] = Best{v1, s};
+                            if (v2 > c[2].v) c[2] = Best{v2, s};
+                            if (v3 > c[3].v) c[3] = Best{v3, s};
+                        }
+                        to_lds(nslot, nslot & 1);
+                        {
+                            const int ahead = done + 1 + PF;
+                            load(first + (ahead < n ? ahead : n - 1), nslot);
+                        }
+                        const Best w = reduce4_best_over_lanes<32>(c[0], c[1], c[2], c[3], lane);
+                        const int col = colw + kk;
+                        if (rowl < 4 && col < T) {
+                            sm.dvec[buf ^ 1][col] = w.v;
+                            bpb[(size_t)i * T + col] = (uint8_t)(w.a == kNoArg ? 0 : w.a);
+                        }
+                        __syncthreads();
+                        buf ^= 1;
+                        if (++done >= n) { running = false; break; }
+                    }
+                }
+            }
+        } else {
+            run(e, h + 1, -1, bwd_step);
+        }
+    } else {
+        if (dir == 0) run(p0 + 1, h, +1, fwd_step);
+        else run(e, h + 1, -1, bwd_step);
+    }
     if (tid < T) mid[tid] = sm.dvec[buf][tid];
 }
 
@@ -279,8 +379,16 @@ __global__ __launch_bounds__(128) void viterbi_trace_kernel(VitArgs a) {
 
 template <typename G, typename TIN, bool ALIGNED>
 static hipError_t launch_geo(const VitArgs& a, hipStream_t st) {
-    hipLaunchKernelGGL((viterbi_half_kernel<G, TIN, ALIGNED>), dim3(2 * a.B * a.C), dim3(G::W), 0, st, a);
-    hipError_t e = hipGetLastError();
+    hipError_t e = hipSuccess;
+    size_t turn_bytes = 0;
+    if constexpr (vit_turns<G, ALIGNED>()) {
+        turn_bytes = kTurnFloats * sizeof(float);
+        e = hipFuncSetAttribute(reinterpret_cast<const void*>(&viterbi_half_kernel<G, TIN, ALIGNED>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)turn_bytes);
+        if (e != hipSuccess) return e;
+    }
+    hipLaunchKernelGGL((viterbi_half_kernel<G, TIN, ALIGNED>), dim3(2 * a.B * a.C), dim3(G::W), turn_bytes, st, a);
+    e = hipGetLastError();
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(viterbi_trace_kernel, dim3(a.B * a.C), dim3(128), 0, st, a);
     return hipGetLastError();
