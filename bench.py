@@ -167,7 +167,8 @@ def main():
     # With few sequences and T = 128 that pass is the two-workgroups-per-chain kernel (plus two
     # few-microsecond helpers the event interval also covers: mailbox reset, exact fix-up launch).
     paired = w.T == 128 and 4 * w.B <= torch.cuda.get_device_properties(dev).multi_processor_count
-    roofline = {"bound": "hbm", "kernel": "pair_marginal_kernel" if paired else "chain_marginal_kernel",
+    kernel = "pair_marginal_kernel" if paired else ("wave_marginal_kernel" if w.T <= 32 else "chain_marginal_kernel")
+    roofline = {"bound": "hbm", "kernel": kernel,
                 "achieved": achieved, "peak": HBM_PEAK_GBPS,
                 "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS, "traffic": stored_traffic(w.key),
                 "algorithmic_bytes_per_launch": alg_bytes, "avg_launch_ms": pass2_avg,
