@@ -371,3 +371,10 @@ def test_paper_benchmark_shape(crf, oracle_mod):
     want_lz, want_mu = oracle_mod.marginals(phi[pick].contiguous(), None)
     _close_logz(lz.cpu().numpy()[pick], want_lz, "paper shape")
     assert np.abs(mu[pick].cpu().numpy() - want_mu).max() <= 1e-5
+
+
+def test_paper_hmm_shape(crf, oracle_mod):
+    """The paper's HMM size (same appendix table): one chain, n=128, 32 states: a single sequence
+    leaves all parallelism to the two chains."""
+    w = workloads.WORKLOADS["paper_hmm"]
+    check_case(crf, oracle_mod, workloads.phi_batch(w), workloads.lengths(w), what="paper hmm shape")
