@@ -37,6 +37,10 @@ def _load():
     lib.lccrf_oracle_marginals.restype = i
     lib.lccrf_oracle_viterbi.argtypes = [vp, i, ip, i, i, i, dp, vp, dp]
     lib.lccrf_oracle_viterbi.restype = i
+    lib.lccrf_oracle_log_prob.argtypes = [vp, i, ip, ip, i, i, i, dp]
+    lib.lccrf_oracle_log_prob.restype = i
+    lib.lccrf_oracle_cross_entropy.argtypes = [vp, vp, i, ip, i, i, i, dp]
+    lib.lccrf_oracle_cross_entropy.restype = i
     lib.lccrf_oracle_threads.argtypes = []
     lib.lccrf_oracle_threads.restype = i
     _lib = lib
@@ -149,3 +153,36 @@ def viterbi(phi, lengths=None, with_gap: bool = True):
     if rc != 0:
         raise RuntimeError(f"oracle error {rc}")
     return score, tags, gap
+
+
+def log_prob(phi, tags, lengths=None) -> np.ndarray:
+    """log p(tags) [B] float64: the path's score minus logZ (NaN where a tag is out of range)."""
+    lib = _load()
+    arr, dt, (B, N, T, T2) = _as_storage(phi)
+    assert T == T2
+    l = _lengths(lengths, B)
+    y = np.ascontiguousarray(np.asarray(tags), dtype=np.int32)
+    assert y.shape == (B, N)
+    out = np.empty((B,))
+    rc = lib.lccrf_oracle_log_prob(_ptr(arr), dt, _ptr(l), _ptr(y), B, N, T, _ptr(out))
+    if rc != 0:
+        raise RuntimeError(f"oracle error {rc}")
+    return out
+
+
+def cross_entropy(phi_p, phi_q, lengths=None) -> np.ndarray:
+    """H(p, q) [B] float64 = logZ_q - sum_e p(e) phi_q(e); entropy is cross_entropy(phi, phi)."""
+    lib = _load()
+    arr_p, dt, (B, N, T, T2) = _as_storage(phi_p)
+    arr_q, dt_q, shape_q = _as_storage(phi_q)
+    assert T == T2 and dt == dt_q and tuple(shape_q) == (B, N, T, T)
+    l = _lengths(lengths, B)
+    out = np.empty((B,))
+    rc = lib.lccrf_oracle_cross_entropy(_ptr(arr_p), _ptr(arr_q), dt, _ptr(l), B, N, T, _ptr(out))
+    if rc != 0:
+        raise RuntimeError(f"oracle error {rc}")
+    return out
+
+
+def entropy(phi, lengths=None) -> np.ndarray:
+    return cross_entropy(phi, phi, lengths)

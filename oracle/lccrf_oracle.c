@@ -22,7 +22,9 @@
  *     Eq. 3 and Eq. 4) in their closed forward-backward form
  *   - the same recursion in the max-plus semiring (section "Computing Most
  *     Probable Structure")                              -> best path, its score,
- *     and the gap to the second-best path via max-marginals.
+ *     and the gap to the second-best path via max-marginals
+ *   - log-probability of a given path (Eq. 2) and cross-entropy / entropy from the
+ *     marginals (section "Entropy and KL Divergence"), as those formulas stand.
  *
  * No blocking, fusion or reordering: loops over b, i, s, t; every log-sum-exp is
  * shifted by its own maximum.  The only parallelism is an OpenMP loop over the
@@ -177,6 +179,79 @@ int lccrf_oracle_marginals(const void *phi, int dtype, const int32_t *lengths,
                     }
         }
         free(alpha); free(beta); free(tmp);
+    }
+    return err ? -2 : 0;
+}
+
+/*
+ * log p(y) = score(y) - logZ for one given tag path per sequence (section "Structured
+ * Distributions", Eq. 2, numerator and denominator of the probability of a structure).
+ * tags[b][i], i < L, must lie in [0, T); otherwise out[b] = NaN.  Empty chain: log p = 0.
+ */
+int lccrf_oracle_log_prob(const void *phi, int dtype, const int32_t *lengths, const int32_t *tags,
+                          int B, int N, int T, double *out)
+{
+    if (!phi || !tags || !out || B < 1 || N < 1 || T < 1 || (dtype != 0 && dtype != 1)) return -1;
+    double *logZ = (double *)malloc(sizeof(double) * (size_t)B);
+    if (!logZ) return -2;
+    int rc = lccrf_oracle_log_partition(phi, dtype, lengths, B, N, T, logZ);
+    if (rc != 0) { free(logZ); return rc; }
+    for (int b = 0; b < B; ++b) {
+        int L = clamp_len(lengths, b, N);
+        size_t base = (size_t)b * N * T * T;
+        const int32_t *y = tags + (size_t)b * N;
+        double sc = 0.0;
+        int ok = 1;
+        for (int i = 0; i < L; ++i)
+            if (y[i] < 0 || y[i] >= T) ok = 0;
+        if (ok && L > 0) {
+            sc = phi_at(phi, dtype, base + (size_t)y[0]);
+            for (int i = 1; i < L; ++i)
+                sc += phi_at(phi, dtype, base + (size_t)i * T * T + (size_t)y[i - 1] * T + (size_t)y[i]);
+        }
+        out[b] = ok ? sc - logZ[b] : NAN;
+    }
+    free(logZ);
+    return 0;
+}
+
+/*
+ * Cross-entropy of two chains over the same edges (section "Entropy and KL Divergence"):
+ *     H(p, q) = logZ_q - sum_e p(e) phi_q(e),
+ * p(e) the edge marginals of p, the sum running over the first-tag "edges" (0, 0, t) and the
+ * edges (i, s, t), 1 <= i < L.  Entropy is H(p, p); KL(p || q) = H(p, q) - H(p, p).
+ * An edge with p(e) = 0 contributes nothing whatever phi_q(e) is.  If p has no finite path the
+ * result is NaN.  Empty chain: 0.
+ */
+int lccrf_oracle_cross_entropy(const void *phi_p, const void *phi_q, int dtype, const int32_t *lengths,
+                               int B, int N, int T, double *out)
+{
+    if (!phi_p || !phi_q || !out || B < 1 || N < 1 || T < 1 || (dtype != 0 && dtype != 1)) return -1;
+    size_t esz = dtype == 0 ? 4 : 2;
+    int err = 0;
+    for (int b = 0; b < B; ++b) {   /* one sequence at a time: its marginals are N*T*T doubles */
+        int L = clamp_len(lengths, b, N);
+        if (L == 0) { out[b] = 0.0; continue; }
+        size_t base = (size_t)b * N * T * T;
+        int32_t len1 = L;
+        double *mu = (double *)malloc(sizeof(double) * (size_t)N * T * T);
+        double lzp, lzq;
+        if (!mu) { err = 1; continue; }
+        int rc = lccrf_oracle_marginals((const char *)phi_p + base * esz, dtype, &len1, 1, N, T, &lzp, mu);
+        if (rc == 0) rc = lccrf_oracle_log_partition((const char *)phi_q + base * esz, dtype, &len1, 1, N, T, &lzq);
+        if (rc != 0) { err = 1; free(mu); continue; }
+        if (lzp == -INFINITY) { out[b] = NAN; free(mu); continue; }
+        double acc = 0.0;
+        for (int t = 0; t < T; ++t)
+            if (mu[t] > 0.0) acc += mu[t] * phi_at(phi_q, dtype, base + (size_t)t);
+        for (int i = 1; i < L; ++i)
+            for (int s = 0; s < T; ++s)
+                for (int t = 0; t < T; ++t) {
+                    size_t k = (size_t)i * T * T + (size_t)s * T + t;
+                    if (mu[k] > 0.0) acc += mu[k] * phi_at(phi_q, dtype, base + k);
+                }
+        out[b] = lzq - acc;
+        free(mu);
     }
     return err ? -2 : 0;
 }

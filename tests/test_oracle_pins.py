@@ -351,3 +351,94 @@ def test_workload_generators_are_reproducible():
     lens = workloads.lengths(w)
     assert lens.dtype.is_floating_point is False and lens.shape == (w.B,)
     assert 1.5 < float(a.std()) < 3.0
+
+
+# ---------------------------------------------------------------------------------------
+# log-probability of a path and cross-entropy / entropy / KL (section "Entropy and KL Divergence")
+
+def test_log_prob_sums_to_one_over_all_paths(oracle_mod):
+    """exp(log p(y)) over every path of a small chain is a probability distribution, and each
+    value equals the enumeration's."""
+    T, N = 3, 5
+    phi = _rand(61, 2, N, T, scale=1.5)
+    lens = np.array([5, 3], dtype=np.int32)
+    for b, L in enumerate(lens):
+        paths = brute.all_paths(T, int(L))
+        sc = brute.path_scores(phi[b].astype(np.float64), int(L), paths)
+        want = sc - scipy.special.logsumexp(sc)
+        tags = np.full((len(paths), N), -1, dtype=np.int32)
+        tags[:, :L] = paths
+        rep = np.repeat(phi[b:b + 1], len(paths), axis=0)
+        got = oracle_mod.log_prob(rep, tags, np.full((len(paths),), L, dtype=np.int32))
+        assert np.abs(got - want).max() < 1e-10
+        assert np.exp(got).sum() == pytest.approx(1.0, abs=1e-10)
+
+
+def test_log_prob_special_cases(oracle_mod):
+    phi = _rand(62, 3, 4, 3)
+    tags = np.array([[0, 1, 2, 0], [2, 2, -1, -1], [0, 3, 0, 0]], dtype=np.int32)
+    lens = np.array([4, 2, 4], dtype=np.int32)
+    got = oracle_mod.log_prob(phi, tags, lens)
+    assert np.isnan(got[2])                      # tag 3 does not exist
+    p64 = phi.astype(np.float64)
+    logZ = oracle_mod.log_partition(phi, lens)
+    assert got[1] == pytest.approx(p64[1, 0, 0, 2] + p64[1, 1, 2, 2] - logZ[1], abs=1e-12)
+    assert oracle_mod.log_prob(phi, tags, np.zeros(3, dtype=np.int32)) == pytest.approx(0.0)   # empty chains
+    # the best path is the most probable one
+    score, best, _ = oracle_mod.viterbi(phi, lens)
+    lp_best = oracle_mod.log_prob(phi, best, lens)
+    assert np.allclose(lp_best, score - logZ, atol=1e-12)
+    assert (lp_best[:2] >= got[:2] - 1e-12).all()
+
+
+def test_entropy_closed_forms(oracle_mod):
+    """Zero potentials: the uniform distribution over T^L paths.  Potentials that ignore the previous
+    tag: independent positions, entropies add."""
+    T, N = 4, 6
+    lens = np.array([6, 3, 1, 0], dtype=np.int32)
+    H = oracle_mod.entropy(np.zeros((4, N, T, T), dtype=np.float32), lens)
+    assert np.allclose(H, lens * math.log(T), atol=1e-12)
+    rng = np.random.default_rng(63)
+    e = rng.standard_normal((4, N, T)) * 2.0
+    phi = np.broadcast_to(e[:, :, None, :], (4, N, T, T)).astype(np.float32)
+    e32 = phi[:, :, 0, :].astype(np.float64)
+    logp = e32 - scipy.special.logsumexp(e32, axis=-1, keepdims=True)
+    per_pos = -(np.exp(logp) * logp).sum(-1)
+    want = np.array([per_pos[b, :L].sum() for b, L in enumerate(lens)])
+    assert np.allclose(oracle_mod.entropy(phi, lens), want, atol=1e-10)
+
+
+def test_cross_entropy_against_enumeration(oracle_mod):
+    """H(p, q) = -sum_y p(y) log q(y) by brute force; Gibbs' inequality; KL = 0 for equal
+    distributions even when the potentials differ by per-position constants."""
+    T, N = 3, 6
+    p = _rand(64, 3, N, T, scale=1.5)
+    q = _rand(65, 3, N, T, scale=1.0)
+    lens = np.array([6, 4, 1], dtype=np.int32)
+    Hpq = oracle_mod.cross_entropy(p, q, lens)
+    Hp = oracle_mod.entropy(p, lens)
+    for b, L in enumerate(lens):
+        paths = brute.all_paths(T, int(L))
+        sp = brute.path_scores(p[b].astype(np.float64), int(L), paths)
+        sq = brute.path_scores(q[b].astype(np.float64), int(L), paths)
+        lp = sp - scipy.special.logsumexp(sp)
+        lq = sq - scipy.special.logsumexp(sq)
+        assert Hpq[b] == pytest.approx(-(np.exp(lp) * lq).sum(), abs=1e-10)
+        assert Hp[b] == pytest.approx(-(np.exp(lp) * lp).sum(), abs=1e-10)
+        assert Hpq[b] >= Hp[b] - 1e-12
+    shift = np.random.default_rng(66).standard_normal((3, N, 1, 1)).astype(np.float32)
+    same = (p.astype(np.float64) + shift).astype(np.float32)
+    kl = oracle_mod.cross_entropy(p, same, lens) - Hp
+    assert np.abs(kl).max() < 1e-5      # float32 rounding of the shifted copy only
+
+
+def test_entropy_with_forbidden_edges(oracle_mod):
+    """-inf potentials carry no probability and must not poison the sum (0 * -inf)."""
+    phi = _rand(67, 1, 5, 3)
+    phi[0, 2, :, 1] = -np.inf
+    phi[0, 4, 0, :] = -np.inf
+    r = brute.enumerate_sequence(phi[0].astype(np.float64), 5)
+    assert oracle_mod.entropy(phi)[0] == pytest.approx(r["entropy"], abs=1e-10)
+    dead = phi.copy()
+    dead[0, 3] = -np.inf
+    assert np.isnan(oracle_mod.entropy(dead)[0])
