@@ -50,7 +50,13 @@ extern "C" {
 
 typedef enum { LCCRF_F32 = 0, LCCRF_BF16 = 1 } lccrf_dtype;
 
-typedef enum { LCCRF_OP_LOGZ = 0, LCCRF_OP_MARGINALS = 1, LCCRF_OP_ARGMAX = 2 } lccrf_op;
+typedef enum {
+    LCCRF_OP_LOGZ = 0,
+    LCCRF_OP_MARGINALS = 1,
+    LCCRF_OP_ARGMAX = 2,
+    LCCRF_OP_LOG_PROB = 3,
+    LCCRF_OP_ENTROPY = 4
+} lccrf_op;
 
 /* How the recursion over positions is scheduled.  Results are the same up to
  * rounding; AUTO picks by shape. */
@@ -145,6 +151,31 @@ int lccrf_marginals_timed(const void* phi, lccrf_dtype dt, const int32_t* length
                           int B, int N, int T, float* logZ, float* marginals,
                           void* workspace, size_t workspace_bytes, void* stream, lccrf_algo algo,
                           void* ev_begin, void* ev_between, void* ev_end);
+
+/*
+ * log p(y) = score(y) - logZ of one given tag path per sequence (paper, section "Structured
+ * Distributions", Eq. 2: the probability of a structure; section "Computing Probability of a
+ * Structure and Partition Function").
+ *   tags      [B][N] int32 (device), tags[b][i] in [0, T) for i < length; entries past the length
+ *             are ignored.  A tag out of range makes log_prob[b] NaN (nothing out of bounds is read).
+ *   log_prob  [B] float32 (device).  Empty chain: 0.
+ * The score and logZ are combined in double precision; one read of phi plus N gathers.
+ * Workspace: lccrf_workspace_bytes(LCCRF_OP_LOG_PROB, ...).  Errors as lccrf_log_partition.
+ */
+int lccrf_log_prob(const void* phi, lccrf_dtype dt, const int32_t* lengths, const int32_t* tags,
+                   int B, int N, int T, float* log_prob,
+                   void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Entropy H(p) = -sum_y p(y) log p(y) of every chain, in nats (paper, section "Entropy and KL
+ * Divergence": H(p) = H(p, p) = logZ - sum_e p(e) phi(e)).  Computed in ONE read of phi and without
+ * forming the marginals: the two half chains carry the conditional entropy of the path behind
+ * them, and the meeting position combines them (the same value up to rounding).
+ *   entropy   [B] float32 (device).  Empty chain: 0.  No finite path: NaN.
+ * Workspace: lccrf_workspace_bytes(LCCRF_OP_ENTROPY, ...).  Errors as lccrf_log_partition.
+ */
+int lccrf_entropy(const void* phi, lccrf_dtype dt, const int32_t* lengths, int B, int N, int T,
+                  float* entropy, void* workspace, size_t workspace_bytes, void* stream);
 
 /* Positions per chunk of LCCRF_ALGO_SCAN: a process-wide tuning knob (default 64; 0 restores the
  * default; values outside [4, 4096] return LCCRF_EINVAL and change nothing).  It enters

@@ -23,14 +23,15 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "liblccrf.so")
 
 LCCRF_F32, LCCRF_BF16 = 0, 1
-OP_LOGZ, OP_MARGINALS, OP_ARGMAX = 0, 1, 2
+OP_LOGZ, OP_MARGINALS, OP_ARGMAX, OP_LOG_PROB, OP_ENTROPY = 0, 1, 2, 3, 4
 ALGO_AUTO, ALGO_SEQUENTIAL, ALGO_SCAN, ALGO_SEQUENTIAL_EXACT = 0, 1, 2, 3
 MAX_T = 256
 
 EXPORTS = (
     "lccrf_workspace_bytes", "lccrf_log_partition", "lccrf_marginals", "lccrf_argmax",
     "lccrf_log_partition_algo", "lccrf_marginals_algo", "lccrf_argmax_algo",
-    "lccrf_marginals_timed", "lccrf_set_scan_chunk", "lccrf_strerror", "lccrf_version",
+    "lccrf_marginals_timed", "lccrf_log_prob", "lccrf_entropy", "lccrf_set_scan_chunk", "lccrf_strerror",
+    "lccrf_version",
 )
 
 _lib = None
@@ -67,6 +68,10 @@ def load_library() -> ctypes.CDLL:
     lib.lccrf_strerror.argtypes = [i]
     lib.lccrf_strerror.restype = ctypes.c_char_p
     lib.lccrf_version.argtypes = []
+    lib.lccrf_log_prob.argtypes = [vp, i, vp, vp, i, i, i, vp, vp, sz, vp]
+    lib.lccrf_log_prob.restype = i
+    lib.lccrf_entropy.argtypes = base + [vp, vp, sz, vp]
+    lib.lccrf_entropy.restype = i
     lib.lccrf_set_scan_chunk.argtypes = [i]
     lib.lccrf_set_scan_chunk.restype = i
     _lib = lib
@@ -184,6 +189,38 @@ def lccrf_argmax(phi: torch.Tensor, lengths: Optional[torch.Tensor] = None, *,
                                    _stream(phi.device), algo)
     _check(rc, "lccrf_argmax")
     return score, out
+
+
+def lccrf_log_prob(phi: torch.Tensor, tags: torch.Tensor, lengths: Optional[torch.Tensor] = None, *,
+                   out: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """log p(tags) [B] float32: the path's score minus logZ (tags int32 [B, N] on phi's device)."""
+    lib = load_library()
+    dt, B, N, T = _phi_args(phi)
+    if tags.dtype != torch.int32 or tuple(tags.shape) != (B, N) or not tags.is_contiguous() or tags.device != phi.device:
+        raise LccrfError("tags must be a contiguous int32 [B, N] tensor on phi's device")
+    ws, nws = _workspace(OP_LOG_PROB, B, N, T, dt, phi.device, workspace)
+    if out is None:
+        out = torch.empty(B, dtype=torch.float32, device=phi.device)
+    with torch.cuda.device(phi.device):
+        rc = lib.lccrf_log_prob(phi.data_ptr(), dt, _len_ptr(lengths, B, phi.device), tags.data_ptr(), B, N, T,
+                                out.data_ptr(), ws.data_ptr(), nws, _stream(phi.device))
+    _check(rc, "lccrf_log_prob")
+    return out
+
+
+def lccrf_entropy(phi: torch.Tensor, lengths: Optional[torch.Tensor] = None, *,
+                  out: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """Entropy [B] float32 (nats) of every chain."""
+    lib = load_library()
+    dt, B, N, T = _phi_args(phi)
+    ws, nws = _workspace(OP_ENTROPY, B, N, T, dt, phi.device, workspace)
+    if out is None:
+        out = torch.empty(B, dtype=torch.float32, device=phi.device)
+    with torch.cuda.device(phi.device):
+        rc = lib.lccrf_entropy(phi.data_ptr(), dt, _len_ptr(lengths, B, phi.device), B, N, T,
+                               out.data_ptr(), ws.data_ptr(), nws, _stream(phi.device))
+    _check(rc, "lccrf_entropy")
+    return out
 
 
 def lccrf_marginals_timed(phi: torch.Tensor, lengths: Optional[torch.Tensor], out: torch.Tensor,

@@ -15,6 +15,7 @@ int g_scan_chunk = kDefaultScanChunk;
 struct SumWorkspace {
     size_t ua, ub, Oa, Ob, mail, failed;
     size_t Pl, rel, base, Fv, OF, Gv, OG;  // chunked scan (T <= 16 only, else empty)
+    size_t lz64, ha, hb;                   // log-probability and entropy queries
     size_t total;
 };
 inline SumWorkspace sum_workspace(size_t B, size_t N, size_t T) {
@@ -34,6 +35,9 @@ inline SumWorkspace sum_workspace(size_t B, size_t N, size_t T) {
     w.OF = off; off += round_up(BC * sizeof(double));
     w.Gv = off; off += round_up(BC * T * sizeof(float));
     w.OG = off; off += round_up(BC * sizeof(double));
+    w.lz64 = off; off += round_up(B * sizeof(double));
+    w.ha = off; off += round_up(B * T * sizeof(float));
+    w.hb = off; off += round_up(B * T * sizeof(float));
     w.total = off;
     return w;
 }
@@ -134,7 +138,9 @@ size_t lccrf_workspace_bytes(lccrf_op op, int B, int N, int T, lccrf_dtype dt) {
     if (!shape_ok(B, N, T) || !dtype_ok(dt)) return 0;
     switch (op) {
         case LCCRF_OP_LOGZ:
-        case LCCRF_OP_MARGINALS: return sum_workspace(B, N, T).total;
+        case LCCRF_OP_MARGINALS:
+        case LCCRF_OP_LOG_PROB:
+        case LCCRF_OP_ENTROPY: return sum_workspace(B, N, T).total;
         case LCCRF_OP_ARGMAX: return max_workspace(B, N, T).total;
         default: return 0;
     }
@@ -203,6 +209,50 @@ int lccrf_argmax(const void* phi, lccrf_dtype dt, const int32_t* lengths, int B,
                              LCCRF_ALGO_AUTO);
 }
 
+int lccrf_log_prob(const void* phi, lccrf_dtype dt, const int32_t* lengths, const int32_t* tags, int B, int N, int T,
+                   float* log_prob, void* workspace, size_t workspace_bytes, void* stream) {
+    const size_t need = lccrf_workspace_bytes(LCCRF_OP_LOG_PROB, B, N, T, dt);
+    const int rc = check_common(phi, dt, B, N, T, workspace, workspace_bytes, need, LCCRF_ALGO_AUTO);
+    if (rc != LCCRF_OK) return rc;
+    if (!tags || !log_prob) return LCCRF_ENULL;
+    if (!aligned_to(tags, 4) || !aligned_to(log_prob, 4) || (lengths && !aligned_to(lengths, 4))) return LCCRF_EALIGN;
+    const SumWorkspace w = sum_workspace(B, N, T);
+    char* base = static_cast<char*>(workspace);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    double* lz64 = reinterpret_cast<double*>(base + w.lz64);
+    hipError_t e;
+    if (scan_pays(B, N, T))
+        e = lccrf::launch_scan_boundaries(dt, phi, lengths, B, N, T, g_scan_chunk, reinterpret_cast<float*>(base + w.Pl),
+                                          reinterpret_cast<float*>(base + w.rel), reinterpret_cast<double*>(base + w.base),
+                                          reinterpret_cast<float*>(base + w.Fv), reinterpret_cast<double*>(base + w.OF),
+                                          reinterpret_cast<float*>(base + w.Gv), reinterpret_cast<double*>(base + w.OG),
+                                          nullptr, false, st, lz64);
+    else
+        e = lccrf::launch_sequential_sum(0, dt, phi, lengths, B, N, T, reinterpret_cast<float*>(base + w.ua),
+                                         reinterpret_cast<float*>(base + w.ub), reinterpret_cast<double*>(base + w.Oa),
+                                         reinterpret_cast<double*>(base + w.Ob), nullptr, nullptr, st, nullptr, false,
+                                         nullptr, nullptr, lz64);
+    if (e == hipSuccess) e = lccrf::launch_path_log_prob(dt, phi, lengths, tags, B, N, T, lz64, log_prob, st);
+    return e == hipSuccess ? LCCRF_OK : LCCRF_ELAUNCH;
+}
+
+int lccrf_entropy(const void* phi, lccrf_dtype dt, const int32_t* lengths, int B, int N, int T, float* entropy,
+                  void* workspace, size_t workspace_bytes, void* stream) {
+    const size_t need = lccrf_workspace_bytes(LCCRF_OP_ENTROPY, B, N, T, dt);
+    const int rc = check_common(phi, dt, B, N, T, workspace, workspace_bytes, need, LCCRF_ALGO_AUTO);
+    if (rc != LCCRF_OK) return rc;
+    if (!entropy) return LCCRF_ENULL;
+    if (!aligned_to(entropy, 4) || (lengths && !aligned_to(lengths, 4))) return LCCRF_EALIGN;
+    const SumWorkspace w = sum_workspace(B, N, T);
+    char* base = static_cast<char*>(workspace);
+    const hipError_t e = lccrf::launch_entropy(
+        dt, phi, lengths, B, N, T, reinterpret_cast<float*>(base + w.ua), reinterpret_cast<float*>(base + w.ub),
+        reinterpret_cast<double*>(base + w.Oa), reinterpret_cast<double*>(base + w.Ob),
+        reinterpret_cast<float*>(base + w.ha), reinterpret_cast<float*>(base + w.hb), entropy,
+        static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? LCCRF_OK : LCCRF_ELAUNCH;
+}
+
 const char* lccrf_strerror(int code) {
     switch (code) {
         case LCCRF_OK: return "ok";
@@ -223,6 +273,6 @@ int lccrf_set_scan_chunk(int chunk) {
     return LCCRF_OK;
 }
 
-int lccrf_version(void) { return 101; }
+int lccrf_version(void) { return 102; }
 
 }  // extern "C"

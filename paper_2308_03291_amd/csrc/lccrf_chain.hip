@@ -751,7 +751,8 @@ __global__ __launch_bounds__(64) void logz_combine_kernel(ChainArgs a) {
     const int N = a.N, T = a.T;
     const int L = clamp_length(a.lengths, b, N);
     if (L == 0) {
-        if (lane == 0) a.logZ[b] = 0.f;
+        if (lane == 0 && a.logZ) a.logZ[b] = 0.f;
+        if (lane == 0 && a.logZ64) a.logZ64[b] = 0.0;
         return;
     }
     const int h = meeting_point(0, L - 1);
@@ -765,7 +766,9 @@ __global__ __launch_bounds__(64) void logz_combine_kernel(ChainArgs a) {
     float S = 0.f;
     for (int t = lane; t < T; t += 64) S += ex2(ua[t] + ub[t] - g);
     S = xor_sum<1, 64>(S);
-    if (lane == 0) a.logZ[b] = (float)(((double)(m + lg2(S)) + a.Oa[vb + h] + a.Ob[vb + h]) * kLn2);
+    const double lz = ((double)(m + lg2(S)) + a.Oa[vb + h] + a.Ob[vb + h]) * kLn2;
+    if (lane == 0 && a.logZ) a.logZ[b] = (float)lz;
+    if (lane == 0 && a.logZ64) a.logZ64[b] = lz;
 }
 
 // ---------------------------------------------------------------------------------------
@@ -836,8 +839,9 @@ static hipError_t launch_wave(int op, int dtype, const ChainArgs& a, hipStream_t
 hipError_t launch_sequential_sum(int op, int dtype, const void* phi, const int32_t* lengths, int B, int N, int T,
                                  float* ua, float* ub, double* Oa, double* Ob, float* logZ, float* mu,
                                  hipStream_t st, hipEvent_t between, bool exact_only, unsigned long long* mail,
-                                 int* failed) {
+                                 int* failed, double* logZ64) {
     ChainArgs a{phi, lengths, B, N, T, ua, ub, Oa, Ob, logZ, mu, exact_only ? 1 : 0, nullptr, 0, 1, nullptr, nullptr, nullptr, nullptr};
+    a.logZ64 = logZ64;
     if (wave_supported(T)) return launch_wave(op, dtype, a, st, between);
     // Pairs pay off when one workgroup per chain would leave at least half of the chip idle.
     static const int cus = [] {

@@ -31,6 +31,11 @@ struct ChainArgs {
     unsigned long long* pair_mail;
     int* pair_failed;
     int pair_words;
+    double* logZ64;  // [B] or null: logZ in double precision (natural logarithm), for log-probabilities
+    // Entropy mode (ha non-null, first pass only): the chains also carry the conditional entropy of
+    // the path behind them given the current tag, and leave it here for the meeting position.
+    float* ha;  // [B][T] H(y_0 .. y_{h-1} | y_h = t), base-2
+    float* hb;  // [B][T] H(y_{h+1} .. y_{L-1} | y_h = t), base-2
 };
 
 // The stretch of positions one pair of workgroups handles: all of a sequence, or one chunk.

@@ -340,6 +340,11 @@ __device__ __forceinline__ void store4(float* __restrict__ mu_out, int T, int s,
     }
 }
 
+// Pieces of the conditional-entropy recursion: with e = 2^arg the shifted exponentials of a step,
+// S = sum e and U = sum e (h - arg), the new entropy is U / S + log2 S (0 for an unreachable tag).
+__device__ __forceinline__ float log2_term(float arg) { return fmaxf(arg, -200.f); }  // 2^arg is 0 below: keeps 0 * inf away
+__device__ __forceinline__ float entropy_of(float U, float S) { return S > 0.f ? U * __builtin_amdgcn_rcpf(S) + __builtin_amdgcn_logf(S) : 0.f; }
+
 __device__ __forceinline__ float finite_or_zero(float m) { return (m == LCCRF_NEG_INF) ? 0.0f : m; }
 
 __device__ __forceinline__ int clamp_length(const int32_t* __restrict__ lengths, int b, int N) {

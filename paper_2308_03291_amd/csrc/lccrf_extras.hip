@@ -1,0 +1,288 @@
+// Queries derived from the partition function (paper, sections "Computing Probability of a
+// Structure and Partition Function" and "Entropy and KL Divergence"): the log-probability of
+// a given tag path and the entropy of the distribution.  The heavy part of both is the
+// first pass of the chain kernels; what is here only finishes them.
+#include "lccrf_chain_args.h"
+#include "lccrf_device.h"
+#include "lccrf_launch.h"
+
+namespace lccrf {
+
+// log p(y) = phi[0][0][y_0] + sum_i phi[i][y_{i-1}][y_i] - logZ.  One wave per sequence; the
+// score is summed in double precision (it and logZ are both of the size of the chain's total,
+// their difference is not).  A tag outside [0, T) makes the result NaN.
+template <typename TIN>
+__global__ __launch_bounds__(64) void path_log_prob_kernel(const TIN* __restrict__ phi, const int32_t* __restrict__ lengths,
+                                                          const int32_t* __restrict__ tags, int N, int T,
+                                                          const double* __restrict__ logZ64, float* __restrict__ out) {
+    const int b = blockIdx.x, lane = threadIdx.x;
+    const int L = clamp_length(lengths, b, N);
+    const int32_t* y = tags + (size_t)b * N;
+    const TIN* phib = phi + (size_t)b * N * T * T;
+    double acc = 0.0;
+    bool bad = false;
+    for (int i = lane; i < L; i += 64) {
+        const int t = y[i], s = i > 0 ? y[i - 1] : 0;
+        if (t < 0 || t >= T || s < 0 || s >= T) { bad = true; continue; }
+        acc += (double)Elem<TIN>::get(phib + (size_t)i * T * T + (size_t)s * T + t);
+    }
+    acc += lane_xor<1>(acc);
+    acc += lane_xor<2>(acc);
+    acc += lane_xor<4>(acc);
+    acc += lane_xor<8>(acc);
+    acc += lane_xor<16>(acc);
+    acc += lane_xor<32>(acc);
+    const bool any_bad = __builtin_amdgcn_ballot_w64(bad) != 0;
+    if (lane == 0) out[b] = any_bad ? __builtin_nanf("") : (float)(acc - logZ64[b]);
+}
+
+hipError_t launch_path_log_prob(int dtype, const void* phi, const int32_t* lengths, const int32_t* tags, int B, int N,
+                                int T, const double* logZ64, float* out, hipStream_t st) {
+    if (dtype == 0)
+        hipLaunchKernelGGL(path_log_prob_kernel<float>, dim3(B), dim3(64), 0, st, static_cast<const float*>(phi), lengths,
+                           tags, N, T, logZ64, out);
+    else
+        hipLaunchKernelGGL(path_log_prob_kernel<uint16_t>, dim3(B), dim3(64), 0, st, static_cast<const uint16_t*>(phi),
+                           lengths, tags, N, T, logZ64, out);
+    return hipGetLastError();
+}
+
+// Entropy from what the two half chains leave at the meeting position h.  With the Markov
+// property p(y) = p(y_h) p(y_<h | y_h) p(y_>h | y_h), so
+//     H = H(y_h) + sum_t p(y_h = t) [ H(y_<h | y_h = t) + H(y_>h | y_h = t) ],
+// the two conditional entropies being what the chains carried along (ha, hb, base 2) and
+// p(y_h = t) the softmax of alpha_h + beta_h.  One wave per sequence.  No finite path: NaN.
+__global__ __launch_bounds__(64) void entropy_combine_kernel(ChainArgs a, float* __restrict__ H) {
+    const int b = blockIdx.x, lane = threadIdx.x;
+    const int N = a.N, T = a.T;
+    const int L = clamp_length(a.lengths, b, N);
+    if (L == 0) {
+        if (lane == 0) H[b] = 0.f;
+        return;
+    }
+    const int h = meeting_point(0, L - 1);
+    const size_t vb = (size_t)b * N;
+    const float* ua = a.ua + (vb + h) * T;
+    const float* ub = a.ub + (vb + h) * T;
+    float m = LCCRF_NEG_INF;
+    for (int t = lane; t < T; t += 64) m = fmaxf(m, ua[t] + ub[t]);
+    m = xor_max<1, 64>(m);
+    if (m == LCCRF_NEG_INF) {
+        if (lane == 0) H[b] = __builtin_nanf("");
+        return;
+    }
+    float S = 0.f;
+    for (int t = lane; t < T; t += 64) S += ex2(ua[t] + ub[t] - m);
+    S = xor_sum<1, 64>(S);
+    const float lS = lg2(S);
+    float acc = 0.f;
+    for (int t = lane; t < T; t += 64) {
+        const float z = ua[t] + ub[t] - m;  // log2 of p(y_h = t) S
+        const float p = ex2(z) / S;
+        if (p > 0.f) acc += p * (a.ha[(size_t)b * T + t] + a.hb[(size_t)b * T + t] - (z - lS));
+    }
+    acc = xor_sum<1, 64>(acc);
+    if (lane == 0) H[b] = (float)((double)acc * kLn2);
+}
+
+static hipError_t launch_entropy_combine(const ChainArgs& a, float* H, hipStream_t st) {
+    hipLaunchKernelGGL(entropy_combine_kernel, dim3(a.B), dim3(64), 0, st, a, H);
+    return hipGetLastError();
+}
+
+
+// ---------------------------------------------------------------------------------------
+// Entropy first pass for T > 32 (the one-wave kernels carry it themselves for T <= 32).
+//
+// The same two half chains as chain_half_kernel, each carrying besides its normalised vector
+// the conditional entropy (base 2) of the path behind it given the current tag:
+//     forward:  h_i(t) = sum_s q(s|t) [h_{i-1}(s) - log2 q(s|t)],  q(s|t) = 2^(ua(s) + phi2(s,t)) / S(t)
+//     backward: h_{i-1}(s) = sum_t q(t|s) [h_i(t) - log2 q(t|s)],  q(t|s) = 2^(phi2(s,t) + ub(t)) / S(s)
+// evaluated as U / S + log2 S with U = sum e (h - log2 e) over the shifted exponentials e.
+// Plain exact steps (every sum against its own maximum), a secondary query: the forward step
+// takes the column maxima through LDS first, then the sums.
+template <typename G>
+struct EntropySmem {
+    alignas(16) float pmax[G::WAVES][G::TCAP];
+    alignas(16) float psum[G::WAVES][G::TCAP];
+    alignas(16) float pU[G::WAVES][G::TCAP];
+    alignas(16) float rvec[2][G::TCAP];
+    alignas(16) float hvec[2][G::TCAP];
+    alignas(16) float wmax[2][16];
+};
+
+
+template <typename G, typename TIN, bool ALIGNED>
+__global__ __launch_bounds__(G::W) void entropy_half_kernel(ChainArgs a) {
+    __shared__ EntropySmem<G> sm;
+    constexpr int ITEMS = G::ITEMS, PF = 2;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int b = blockIdx.x >> 1, dir = blockIdx.x & 1;
+    const int N = a.N, T = a.T;
+    const int L = clamp_length(a.lengths, b, N);
+    if (L == 0) return;
+    const int e = L - 1, h = meeting_point(0, e);
+    const int c4 = 4 * (tid % G::LPR), r0 = tid / G::LPR;
+    const size_t TT = (size_t)T * T, vb = (size_t)b * N;
+    const TIN* phib = static_cast<const TIN*>(a.phi) + (size_t)b * N * TT;
+
+    for (int k = tid; k < 2 * G::TCAP; k += G::W) {
+        (&sm.rvec[0][0])[k] = LCCRF_NEG_INF;
+        (&sm.hvec[0][0])[k] = 0.f;
+    }
+    if (tid < 32) (&sm.wmax[0][0])[tid] = LCCRF_NEG_INF;
+    __syncthreads();
+    if (tid < T) sm.rvec[0][tid] = dir == 0 ? Elem<TIN>::get(phib + tid) * kLog2e : 0.f;
+    __syncthreads();
+
+    float ring[PF][ITEMS][4];
+    auto load = [&](int i, int slot) { load_tile<G, TIN, ALIGNED>(phib + (size_t)i * TT, T, c4, r0, ring[slot]); };
+    double O = 0.0;
+    int buf = 0;
+    auto shift = [&]() {  // normaliser of the vector in rvec[buf]: its maximum, by every thread
+        float d = LCCRF_NEG_INF;
+        for (int t = lane; t < T; t += 64) d = fmaxf(d, sm.rvec[buf][t]);
+        return finite_or_zero(xor_max<1, 64>(d));
+    };
+
+    if (dir == 0) {
+        walk<PF>(1, h, +1, load, [&](int, int slot) {
+            float (&x)[ITEMS][4] = ring[slot];
+            const float d = shift();
+            O += (double)d;
+            float ua[ITEMS], hin[ITEMS], lm[4] = {LCCRF_NEG_INF, LCCRF_NEG_INF, LCCRF_NEG_INF, LCCRF_NEG_INF};
+#pragma unroll
+            for (int k = 0; k < ITEMS; ++k) {
+                const int s = r0 + k * G::RPP;
+                ua[k] = (s < T) ? sm.rvec[buf][s] - d : LCCRF_NEG_INF;
+                hin[k] = (s < T) ? sm.hvec[buf][s] : 0.f;
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    x[k][j] = __builtin_fmaf(x[k][j], kLog2e, ua[k]);
+                    lm[j] = fmaxf(lm[j], x[k][j]);
+                }
+            }
+#pragma unroll
+            for (int j = 0; j < 4; ++j) lm[j] = xor_max<G::LPR, 64>(lm[j]);
+            if (lane < G::LPR) *reinterpret_cast<float4*>(&sm.pmax[wave][c4]) = make_float4(lm[0], lm[1], lm[2], lm[3]);
+            __syncthreads();
+            float M[4], ls[4] = {0.f, 0.f, 0.f, 0.f}, lu[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                M[j] = LCCRF_NEG_INF;
+#pragma unroll
+                for (int w = 0; w < G::WAVES; ++w) M[j] = fmaxf(M[j], sm.pmax[w][c4 + j]);
+                M[j] = finite_or_zero(M[j]);
+            }
+#pragma unroll
+            for (int k = 0; k < ITEMS; ++k)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const float arg = x[k][j] - M[j];
+                    const float ex = ex2(arg);
+                    ls[j] += ex;
+                    lu[j] = __builtin_fmaf(ex, hin[k] - log2_term(arg), lu[j]);
+                }
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                ls[j] = xor_sum<G::LPR, 64>(ls[j]);
+                lu[j] = xor_sum<G::LPR, 64>(lu[j]);
+            }
+            if (lane < G::LPR) {
+                *reinterpret_cast<float4*>(&sm.psum[wave][c4]) = make_float4(ls[0], ls[1], ls[2], ls[3]);
+                *reinterpret_cast<float4*>(&sm.pU[wave][c4]) = make_float4(lu[0], lu[1], lu[2], lu[3]);
+            }
+            __syncthreads();
+            if (tid < T) {
+                float S = 0.f, U = 0.f, Mt = LCCRF_NEG_INF;
+#pragma unroll
+                for (int w = 0; w < G::WAVES; ++w) {
+                    S += sm.psum[w][tid];
+                    U += sm.pU[w][tid];
+                    Mt = fmaxf(Mt, sm.pmax[w][tid]);
+                }
+                sm.rvec[buf ^ 1][tid] = Mt + lg2(S);  // Mt = -inf gives S = 0: -inf
+                sm.hvec[buf ^ 1][tid] = entropy_of(U, S);
+            }
+            __syncthreads();
+            buf ^= 1;
+        });
+    } else {
+        walk<PF>(e, h + 1, -1, load, [&](int, int slot) {
+            float (&y)[ITEMS][4] = ring[slot];
+            const float d = shift();
+            O += (double)d;
+            float ub[4], hin[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                ub[j] = (c4 + j < T) ? sm.rvec[buf][c4 + j] - d : LCCRF_NEG_INF;
+                hin[j] = (c4 + j < T) ? sm.hvec[buf][c4 + j] : 0.f;
+            }
+#pragma unroll
+            for (int k = 0; k < ITEMS; ++k) {
+#pragma unroll
+                for (int j = 0; j < 4; ++j) y[k][j] = __builtin_fmaf(y[k][j], kLog2e, ub[j]);
+                const float m = xor_max<1, G::LPR>(fmaxf(fmaxf(y[k][0], y[k][1]), fmaxf(y[k][2], y[k][3])));
+                const float g = finite_or_zero(m);
+                float Sl = 0.f, Ul = 0.f;
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const float arg = y[k][j] - g;
+                    const float ex = ex2(arg);
+                    Sl += ex;
+                    Ul = __builtin_fmaf(ex, hin[j] - log2_term(arg), Ul);
+                }
+                const float S = xor_sum<1, G::LPR>(Sl), U = xor_sum<1, G::LPR>(Ul);
+                const int s = r0 + k * G::RPP;
+                if (c4 == 0 && s < T) {
+                    sm.rvec[buf ^ 1][s] = m + lg2(S);
+                    sm.hvec[buf ^ 1][s] = entropy_of(U, S);
+                }
+            }
+            __syncthreads();
+            buf ^= 1;
+        });
+    }
+    // the vectors of the meeting position
+    const float d = shift();
+    O += (double)d;
+    if (tid < T) {
+        (dir == 0 ? a.ua : a.ub)[(vb + h) * T + tid] = sm.rvec[buf][tid] - d;
+        (dir == 0 ? a.ha : a.hb)[(size_t)b * T + tid] = sm.hvec[buf][tid];
+    }
+    if (tid == 0) (dir == 0 ? a.Oa : a.Ob)[vb + h] = O;
+}
+
+template <typename TIN, bool ALIGNED>
+static hipError_t launch_entropy_T(const ChainArgs& a, hipStream_t st) {
+    const dim3 grid(2 * a.B);
+    if (a.T <= 64)
+        hipLaunchKernelGGL((entropy_half_kernel<Geo<16, 4, 4>, TIN, ALIGNED>), grid, dim3(256), 0, st, a);
+    else if (a.T <= 128)
+        hipLaunchKernelGGL((entropy_half_kernel<Geo<32, 16, 4>, TIN, ALIGNED>), grid, dim3(1024), 0, st, a);
+    else
+        hipLaunchKernelGGL((entropy_half_kernel<Geo<64, 16, 16>, TIN, ALIGNED>), grid, dim3(1024), 0, st, a);
+    return hipGetLastError();
+}
+
+// H(p) [B] for every sequence: first pass in entropy mode, then the combination at the meeting point.
+hipError_t launch_entropy(int dtype, const void* phi, const int32_t* lengths, int B, int N, int T, float* ua, float* ub,
+                          double* Oa, double* Ob, float* ha, float* hb, float* H, hipStream_t st) {
+    ChainArgs a{phi, lengths, B, N, T, ua, ub, Oa, Ob, nullptr, nullptr, 0, nullptr, 0, 1, nullptr, nullptr, nullptr, nullptr};
+    a.ha = ha;
+    a.hb = hb;
+    hipError_t e;
+    if (wave_supported(T)) {
+        e = launch_wave_pass(false, dtype, a, st);
+    } else {
+        const bool aligned = (T % 4) == 0;
+        if (dtype == 0)
+            e = aligned ? launch_entropy_T<float, true>(a, st) : launch_entropy_T<float, false>(a, st);
+        else
+            e = aligned ? launch_entropy_T<uint16_t, true>(a, st) : launch_entropy_T<uint16_t, false>(a, st);
+    }
+    if (e != hipSuccess) return e;
+    return launch_entropy_combine(a, H, st);
+}
+
+}  // namespace lccrf

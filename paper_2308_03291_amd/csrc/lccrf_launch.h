@@ -17,7 +17,7 @@ namespace lccrf {
 hipError_t launch_sequential_sum(int op, int dtype, const void* phi, const int32_t* lengths, int B, int N, int T,
                                  float* ua, float* ub, double* Oa, double* Ob, float* logZ, float* mu,
                                  hipStream_t st, hipEvent_t between = nullptr, bool exact_only = false,
-                                 unsigned long long* mail = nullptr, int* failed = nullptr);
+                                 unsigned long long* mail = nullptr, int* failed = nullptr, double* logZ64 = nullptr);
 
 // Paired second pass (two workgroups per chain; lccrf_pair.hip).
 size_t pair_mail_words(int B);
@@ -33,7 +33,12 @@ hipError_t launch_pair_marginals(int dtype, const void* phi, const int32_t* leng
 bool scan_supported(int T);
 hipError_t launch_scan_boundaries(int dtype, const void* phi, const int32_t* lengths, int B, int N, int T, int chunk,
                                   float* Pl, float* rel, double* base, float* Fv, double* OF, float* Gv, double* OG,
-                                  float* logZ, bool with_beta, hipStream_t st);
+                                  float* logZ, bool with_beta, hipStream_t st, double* logZ64 = nullptr);
+
+// log p(y) = score(y) - logZ for one tag path per sequence (lccrf_extras.hip); logZ64: [B] doubles
+// already computed on the same stream.
+hipError_t launch_path_log_prob(int dtype, const void* phi, const int32_t* lengths, const int32_t* tags, int B, int N,
+                                int T, const double* logZ64, float* out, hipStream_t st);
 // Two-pass forward-backward inside every chunk from those boundary vectors (lccrf_chain.hip); chunk >= 4.
 hipError_t launch_chunked_marginals(int dtype, const void* phi, const int32_t* lengths, int B, int N, int T,
                                     float* ua, float* ub, double* Oa, double* Ob, float* mu, int chunk,
@@ -54,5 +59,10 @@ hipError_t launch_scan_pins(int dtype, const void* phi, const int32_t* lengths, 
 // mid: viterbi_mid_doubles(B, C, T) doubles of scratch.
 hipError_t launch_chunked_max(int dtype, const void* phi, const int32_t* lengths, int B, int N, int T, uint8_t* bp,
                               double* mid, int32_t* tags, int chunk, const int32_t* pin, hipStream_t st);
+
+// Entropy H(p) [B] in one read of phi (lccrf_extras.hip, one-wave kernels for T <= 32).  ua / ub / Oa / Ob
+// as for launch_sequential_sum (only the rows of the meeting positions are written); ha, hb: [B][T] floats.
+hipError_t launch_entropy(int dtype, const void* phi, const int32_t* lengths, int B, int N, int T, float* ua, float* ub,
+                          double* Oa, double* Ob, float* ha, float* hb, float* H, hipStream_t st);
 
 }  // namespace lccrf

@@ -49,6 +49,7 @@ struct ScanArgs {
     double* OG;    // [B][C]
     float* logZ;   // [B] or null
     int with_beta;
+    double* logZ64;  // [B] or null: the same in double precision
 };
 
 // First and last position whose matrix belongs to chunk c (first > last: none).
@@ -252,6 +253,7 @@ __global__ __launch_bounds__(64) void chunk_boundary_kernel(ScanArgs a) {
     const int L = clamp_length(a.lengths, b, N);
     if (L == 0) {
         if (dir == 0 && lane == 0 && a.logZ) a.logZ[b] = 0.f;
+        if (dir == 0 && lane == 0 && a.logZ64) a.logZ64[b] = 0.0;
         return;
     }
     if (dir == 1 && !a.with_beta) return;
@@ -296,10 +298,11 @@ __global__ __launch_bounds__(64) void chunk_boundary_kernel(ScanArgs a) {
             if (lane == 0) a.OF[cb + c] = O;
             __syncthreads();
         });
-        if (a.logZ) {
+        if (a.logZ || a.logZ64) {
             // the walk has run at least once (L >= 1): entry t sits in lanes 4t .. 4t+3, count it once
             const float S = xor_sum<1, 64>(q == 0 ? ex2(nv) : 0.f);
-            if (lane == 0) a.logZ[b] = (float)((O + (double)lg2(S)) * kLn2);
+            if (lane == 0 && a.logZ) a.logZ[b] = (float)((O + (double)lg2(S)) * kLn2);
+            if (lane == 0 && a.logZ64) a.logZ64[b] = (O + (double)lg2(S)) * kLn2;
         }
     } else {
         if (lane < 16) vec[0][lane] = (lane < T) ? 0.f : LCCRF_NEG_INF;  // beta at the last position
@@ -503,9 +506,9 @@ bool scan_supported(int T) { return T >= 1 && T <= 16; }
 
 hipError_t launch_scan_boundaries(int dtype, const void* phi, const int32_t* lengths, int B, int N, int T, int chunk,
                                   float* Pl, float* rel, double* base, float* Fv, double* OF, float* Gv, double* OG,
-                                  float* logZ, bool with_beta, hipStream_t st) {
+                                  float* logZ, bool with_beta, hipStream_t st, double* logZ64) {
     const int C = (N + chunk - 1) / chunk;
-    ScanArgs a{phi, lengths, B, N, T, chunk, C, Pl, rel, base, Fv, OF, Gv, OG, logZ, with_beta ? 1 : 0};
+    ScanArgs a{phi, lengths, B, N, T, chunk, C, Pl, rel, base, Fv, OF, Gv, OG, logZ, with_beta ? 1 : 0, logZ64};
     if (dtype == 0)
         hipLaunchKernelGGL(chunk_product_kernel<float>, dim3(B * C), dim3(64), 0, st, a);
     else

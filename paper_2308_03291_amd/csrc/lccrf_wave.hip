@@ -89,16 +89,22 @@ __device__ __forceinline__ float max4(const float (&x)[4]) { return fmaxf(fmaxf(
 // One forward position: r(t) = log2 sum_s 2^(ua(s) + phi2(s,t)), ua in row form, r in column form.
 // With WITH_MU it also writes mu(s,t) = 2^(ua(s) + phi2(s,t) + ubK(t)) and returns their sum.
 // The speculative form shifts everything by c; it stands only if every sum it made is in range.
-template <int TP, bool WITH_MU, bool ALIGNED>
+// With WITH_H it also advances the conditional entropy of the path behind the current tag (base 2):
+//     h_new(t) = sum_s q(s|t) [h(s) - log2 q(s|t)],  q(s|t) = 2^(ua(s) + phi2(s,t)) / sum_s' (same),
+// computed as U(t) / S(t) + log2 S(t) with U(t) = sum_s e(s,t) [h(s) - log2 e(s,t)] for the same
+// shifted exponentials e the step already forms (hin in row form, hout in column form).
+
+template <int TP, bool WITH_MU, bool ALIGNED, bool WITH_H = false>
 __device__ __forceinline__ void wave_fwd_step(float (&v)[WGeo<TP>::R][4], const float (&ua)[WGeo<TP>::R], float c,
                                               const float (&ubK)[4], float* __restrict__ mu_out, int T, int lane,
-                                              bool exact_only, float (&r)[4], float& tot) {
+                                              bool exact_only, float (&r)[4], float& tot,
+                                              const float (&hin)[WGeo<TP>::R], float (&hout)[4]) {
     using W = WGeo<TP>;
     constexpr int R = W::R;
     const int c4 = 4 * (lane % W::CG), s0 = R * (lane / W::CG);
     bool accepted = false;
     if (!exact_only) {
-        float ls[4] = {0.f, 0.f, 0.f, 0.f}, gm[4] = {0.f, 0.f, 0.f, 0.f};
+        float ls[4] = {0.f, 0.f, 0.f, 0.f}, gm[4] = {0.f, 0.f, 0.f, 0.f}, lu[4] = {0.f, 0.f, 0.f, 0.f};
         if (WITH_MU) {
 #pragma unroll
             for (int j = 0; j < 4; ++j) gm[j] = ex2(c + ubK[j]);
@@ -109,8 +115,10 @@ __device__ __forceinline__ void wave_fwd_step(float (&v)[WGeo<TP>::R][4], const 
             float e[4];
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
-                e[j] = ex2(__builtin_fmaf(v[k][j], kLog2e, uac));
+                const float arg = __builtin_fmaf(v[k][j], kLog2e, uac);
+                e[j] = ex2(arg);
                 ls[j] += e[j];
+                if (WITH_H) lu[j] = __builtin_fmaf(e[j], hin[k] - log2_term(arg), lu[j]);
             }
             if (WITH_MU) store4<ALIGNED>(mu_out, T, s0 + k, c4, e[0] * gm[0], e[1] * gm[1], e[2] * gm[2], e[3] * gm[3]);
         }
@@ -122,6 +130,7 @@ __device__ __forceinline__ void wave_fwd_step(float (&v)[WGeo<TP>::R][4], const 
             const bool inm = c4 + j < T;
             r[j] = inm ? c + lg2(S) : LCCRF_NEG_INF;
             ok = ok && (!inm || sum_in_range(S));
+            if (WITH_H) hout[j] = inm ? entropy_of(xor_sum<W::CG, 64>(lu[j]), S) : 0.f;
         }
         accepted = __builtin_amdgcn_ballot_w64(!ok) == 0;
         if (WITH_MU && accepted) tot = xor_sum<1, 64>(part);
@@ -135,7 +144,7 @@ __device__ __forceinline__ void wave_fwd_step(float (&v)[WGeo<TP>::R][4], const 
                 v[k][j] = __builtin_fmaf(v[k][j], kLog2e, ua[k]);
                 lm[j] = fmaxf(lm[j], v[k][j]);
             }
-        float M[4], g[4], ls[4] = {0.f, 0.f, 0.f, 0.f}, gm[4] = {0.f, 0.f, 0.f, 0.f};
+        float M[4], g[4], ls[4] = {0.f, 0.f, 0.f, 0.f}, gm[4] = {0.f, 0.f, 0.f, 0.f}, lu[4] = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             M[j] = xor_max<W::CG, 64>(lm[j]);
@@ -147,8 +156,10 @@ __device__ __forceinline__ void wave_fwd_step(float (&v)[WGeo<TP>::R][4], const 
             float e[4];
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
-                e[j] = ex2(v[k][j] - g[j]);
+                const float arg = v[k][j] - g[j];
+                e[j] = ex2(arg);
                 ls[j] += e[j];
+                if (WITH_H) lu[j] = __builtin_fmaf(e[j], hin[k] - log2_term(arg), lu[j]);
             }
             if (WITH_MU) store4<ALIGNED>(mu_out, T, s0 + k, c4, e[0] * gm[0], e[1] * gm[1], e[2] * gm[2], e[3] * gm[3]);
         }
@@ -157,15 +168,18 @@ __device__ __forceinline__ void wave_fwd_step(float (&v)[WGeo<TP>::R][4], const 
         for (int j = 0; j < 4; ++j) {
             const float S = xor_sum<W::CG, 64>(ls[j]);
             r[j] = (c4 + j < T) ? M[j] + lg2(S) : LCCRF_NEG_INF;  // M = -inf gives S = 0: -inf
+            if (WITH_H) hout[j] = (c4 + j < T) ? entropy_of(xor_sum<W::CG, 64>(lu[j]), S) : 0.f;
         }
     }
 }
 
 // One backward position: r(s) = log2 sum_t 2^(phi2(s,t) + ub(t)), ub in column form, r in row form.
-template <int TP, bool WITH_MU, bool ALIGNED>
+// WITH_H: the conditional entropy of the path ahead of the current tag (hin in column form, hout in row form).
+template <int TP, bool WITH_MU, bool ALIGNED, bool WITH_H = false>
 __device__ __forceinline__ void wave_bwd_step(float (&v)[WGeo<TP>::R][4], const float (&ub)[4], float c,
                                               const float (&uaK)[WGeo<TP>::R], float* __restrict__ mu_out, int T,
-                                              int lane, bool exact_only, float (&r)[WGeo<TP>::R], float& tot) {
+                                              int lane, bool exact_only, float (&r)[WGeo<TP>::R], float& tot,
+                                              const float (&hin)[4], float (&hout)[WGeo<TP>::R]) {
     using W = WGeo<TP>;
     constexpr int R = W::R;
     const int c4 = 4 * (lane % W::CG), s0 = R * (lane / W::CG);
@@ -176,9 +190,13 @@ __device__ __forceinline__ void wave_bwd_step(float (&v)[WGeo<TP>::R][4], const 
         bool ok = true;
 #pragma unroll
         for (int k = 0; k < R; ++k) {
-            float e[4];
+            float e[4], Ul = 0.f;
 #pragma unroll
-            for (int j = 0; j < 4; ++j) e[j] = ex2(__builtin_fmaf(v[k][j], kLog2e, ubc[j]));
+            for (int j = 0; j < 4; ++j) {
+                const float arg = __builtin_fmaf(v[k][j], kLog2e, ubc[j]);
+                e[j] = ex2(arg);
+                if (WITH_H) Ul = __builtin_fmaf(e[j], hin[j] - log2_term(arg), Ul);
+            }
             const float Sl = (e[0] + e[1]) + (e[2] + e[3]);
             if (WITH_MU) {
                 const float f = ex2(c + uaK[k]);
@@ -189,6 +207,7 @@ __device__ __forceinline__ void wave_bwd_step(float (&v)[WGeo<TP>::R][4], const 
             const bool inm = s0 + k < T;
             r[k] = inm ? c + lg2(S) : LCCRF_NEG_INF;
             ok = ok && (!inm || sum_in_range(S));
+            if (WITH_H) hout[k] = inm ? entropy_of(xor_sum<1, W::CG>(Ul), S) : 0.f;
         }
         accepted = __builtin_amdgcn_ballot_w64(!ok) == 0;
         if (WITH_MU && accepted) tot = xor_sum<1, 64>(part);
@@ -201,16 +220,22 @@ __device__ __forceinline__ void wave_bwd_step(float (&v)[WGeo<TP>::R][4], const 
             for (int j = 0; j < 4; ++j) v[k][j] = __builtin_fmaf(v[k][j], kLog2e, ub[j]);
             const float m = xor_max<1, W::CG>(max4(v[k]));
             const float g = finite_or_zero(m);
-            float e[4];
+            float e[4], Ul = 0.f;
 #pragma unroll
-            for (int j = 0; j < 4; ++j) e[j] = ex2(v[k][j] - g);
+            for (int j = 0; j < 4; ++j) {
+                const float arg = v[k][j] - g;
+                e[j] = ex2(arg);
+                if (WITH_H) Ul = __builtin_fmaf(e[j], hin[j] - log2_term(arg), Ul);
+            }
             const float Sl = (e[0] + e[1]) + (e[2] + e[3]);
             if (WITH_MU) {
                 const float f = ex2(g + uaK[k]);
                 store4<ALIGNED>(mu_out, T, s0 + k, c4, e[0] * f, e[1] * f, e[2] * f, e[3] * f);
                 part += Sl * f;
             }
-            r[k] = (s0 + k < T) ? m + lg2(xor_sum<1, W::CG>(Sl)) : LCCRF_NEG_INF;
+            const float S = xor_sum<1, W::CG>(Sl);
+            r[k] = (s0 + k < T) ? m + lg2(S) : LCCRF_NEG_INF;
+            if (WITH_H) hout[k] = (s0 + k < T) ? entropy_of(xor_sum<1, W::CG>(Ul), S) : 0.f;
         }
         if (WITH_MU) tot = xor_sum<1, 64>(part);
     }
@@ -224,7 +249,7 @@ constexpr int wave_ring_depth(int TP, bool second_pass) { return second_pass ? (
 
 // ---------------------------------------------------------------------------------------
 // Pass 1: both half chains, vectors stored.
-template <int TP, typename TIN, bool ALIGNED>
+template <int TP, typename TIN, bool ALIGNED, bool WITH_H>
 __global__ __launch_bounds__(64) void wave_half_kernel(ChainArgs a) {
     using W = WGeo<TP>;
     constexpr int R = W::R, PF = wave_ring_depth(TP, false);
@@ -261,6 +286,7 @@ __global__ __launch_bounds__(64) void wave_half_kernel(ChainArgs a) {
             O += (double)d;
 #pragma unroll
             for (int j = 0; j < 4; ++j) vc[j] -= d;
+            if (WITH_H && pos != h) return d;  // an entropy query needs the vectors of the meeting position only
             if (rg == 0) {
 #pragma unroll
                 for (int j = 0; j < 4; ++j)
@@ -269,13 +295,20 @@ __global__ __launch_bounds__(64) void wave_half_kernel(ChainArgs a) {
             if (lane == 0) a.Oa[vb + pos] = O;
             return d;
         };
+        float hc[4] = {0.f, 0.f, 0.f, 0.f};  // entropy of the path behind each tag, column form
         walk<PF>(p0 + 1, h, +1, load, [&](int i, int slot) {
             const float d = settle(i - 1);
-            float ua[R];
+            float ua[R], hrow[R];
             col_to_row<TP>(vc, ua, lane);
-            wave_fwd_step<TP, false, ALIGNED>(ring[slot], ua, d, none4, nullptr, T, lane, exact_only, vc, tot);
+            if (WITH_H) col_to_row<TP>(hc, hrow, lane);
+            wave_fwd_step<TP, false, ALIGNED, WITH_H>(ring[slot], ua, d, none4, nullptr, T, lane, exact_only, vc, tot, hrow, hc);
         });
         settle(h);
+        if (WITH_H && rg == 0) {
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                if (c4 + j < T) a.ha[(size_t)b * T + c4 + j] = hc[j];
+        }
     } else {
         float vr[R];  // beta, row form
 #pragma unroll
@@ -293,6 +326,7 @@ __global__ __launch_bounds__(64) void wave_half_kernel(ChainArgs a) {
             O += (double)d;
 #pragma unroll
             for (int k = 0; k < R; ++k) vr[k] -= d;
+            if (WITH_H && pos != h) return d;
             if (cg == 0) {
 #pragma unroll
                 for (int k = 0; k < R; ++k)
@@ -301,13 +335,22 @@ __global__ __launch_bounds__(64) void wave_half_kernel(ChainArgs a) {
             if (lane == 0) a.Ob[vb + pos] = O;
             return d;
         };
+        float hr[R];  // entropy of the path ahead of each tag, row form
+#pragma unroll
+        for (int k = 0; k < R; ++k) hr[k] = 0.f;
         walk<PF>(e, h + 1, -1, load, [&](int i, int slot) {
             const float d = settle(i);
-            float ub[4];
+            float ub[4], hcol[4];
             row_to_col<TP>(vr, ub, lane);
-            wave_bwd_step<TP, false, ALIGNED>(ring[slot], ub, d, noneR, nullptr, T, lane, exact_only, vr, tot);
+            if (WITH_H) row_to_col<TP>(hr, hcol, lane);
+            wave_bwd_step<TP, false, ALIGNED, WITH_H>(ring[slot], ub, d, noneR, nullptr, T, lane, exact_only, vr, tot, hcol, hr);
         });
         settle(h);
+        if (WITH_H && cg == 0) {
+#pragma unroll
+            for (int k = 0; k < R; ++k)
+                if (s0 + k < T) a.hb[(size_t)b * T + s0 + k] = hr[k];
+        }
     }
 }
 
@@ -365,6 +408,9 @@ __global__ __launch_bounds__(64) void wave_marginal_kernel(ChainArgs a) {
 
     float ring[PF][R][4];
     float kappa = 0.f, tot = 0.f;
+    float noh_c[4] = {0.f, 0.f, 0.f, 0.f}, noh_r[R];  // no entropy carried in this pass
+#pragma unroll
+    for (int k = 0; k < R; ++k) noh_r[k] = 0.f;
 
     if (dir == 0) {
         double O = a.Oa[vb + h];
@@ -391,7 +437,7 @@ __global__ __launch_bounds__(64) void wave_marginal_kernel(ChainArgs a) {
             float ubK[4];
 #pragma unroll
             for (int j = 0; j < 4; ++j) ubK[j] = (c4 + j < T) ? aux[slot][j] + K : LCCRF_NEG_INF;
-            wave_fwd_step<TP, true, ALIGNED>(ring[slot], ua, d, ubK, mub + (size_t)i * TT, T, lane, exact_only, vc, tot);
+            wave_fwd_step<TP, true, ALIGNED>(ring[slot], ua, d, ubK, mub + (size_t)i * TT, T, lane, exact_only, vc, tot, noh_r, noh_c);
         });
     } else {
         double O = a.Ob[vb + h];
@@ -421,7 +467,7 @@ __global__ __launch_bounds__(64) void wave_marginal_kernel(ChainArgs a) {
             float uaK[R];
 #pragma unroll
             for (int k = 0; k < R; ++k) uaK[k] = (s0 + k < T) ? aux[slot][k] + K : LCCRF_NEG_INF;
-            wave_bwd_step<TP, true, ALIGNED>(ring[slot], ub, d, uaK, mub + (size_t)i * TT, T, lane, exact_only, vr, tot);
+            wave_bwd_step<TP, true, ALIGNED>(ring[slot], ub, d, uaK, mub + (size_t)i * TT, T, lane, exact_only, vr, tot, noh_c, noh_r);
         });
         // position 0: p(y_0 = t) = softmax_t(alpha_0(t) + beta_0(t)) in row 0, zeros elsewhere
         if (!sp.first) return;
@@ -454,8 +500,10 @@ static hipError_t launch_wave_tp(bool second_pass, const ChainArgs& a, hipStream
     const dim3 grid(2 * a.B * a.C);
     if (second_pass)
         hipLaunchKernelGGL((wave_marginal_kernel<TP, TIN, ALIGNED>), grid, dim3(64), 0, st, a);
+    else if (a.ha)
+        hipLaunchKernelGGL((wave_half_kernel<TP, TIN, ALIGNED, true>), grid, dim3(64), 0, st, a);
     else
-        hipLaunchKernelGGL((wave_half_kernel<TP, TIN, ALIGNED>), grid, dim3(64), 0, st, a);
+        hipLaunchKernelGGL((wave_half_kernel<TP, TIN, ALIGNED, false>), grid, dim3(64), 0, st, a);
     return hipGetLastError();
 }
 
