@@ -8,20 +8,23 @@
 
 namespace lccrf {
 
-// log p(y) = phi[0][0][y_0] + sum_i phi[i][y_{i-1}][y_i] - logZ.  One wave per sequence; the
+// log p(y) = phi[0][0][y_0] + sum_i phi[i][y_{i-1}][y_i] - logZ.  One workgroup per sequence; the
 // score is summed in double precision (it and logZ are both of the size of the chain's total,
 // their difference is not).  A tag outside [0, T) makes the result NaN.
+constexpr int kPathThreads = 512;
 template <typename TIN>
-__global__ __launch_bounds__(64) void path_log_prob_kernel(const TIN* __restrict__ phi, const int32_t* __restrict__ lengths,
+__global__ __launch_bounds__(kPathThreads) void path_log_prob_kernel(const TIN* __restrict__ phi, const int32_t* __restrict__ lengths,
                                                           const int32_t* __restrict__ tags, int N, int T,
                                                           const double* __restrict__ logZ64, float* __restrict__ out) {
-    const int b = blockIdx.x, lane = threadIdx.x;
+    __shared__ double part[kPathThreads / 64];
+    __shared__ int part_bad[kPathThreads / 64];
+    const int b = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int L = clamp_length(lengths, b, N);
     const int32_t* y = tags + (size_t)b * N;
     const TIN* phib = phi + (size_t)b * N * T * T;
     double acc = 0.0;
     bool bad = false;
-    for (int i = lane; i < L; i += 64) {
+    for (int i = tid; i < L; i += kPathThreads) {
         const int t = y[i], s = i > 0 ? y[i - 1] : 0;
         if (t < 0 || t >= T || s < 0 || s >= T) { bad = true; continue; }
         acc += (double)Elem<TIN>::get(phib + (size_t)i * T * T + (size_t)s * T + t);
@@ -32,17 +35,30 @@ __global__ __launch_bounds__(64) void path_log_prob_kernel(const TIN* __restrict
     acc += lane_xor<8>(acc);
     acc += lane_xor<16>(acc);
     acc += lane_xor<32>(acc);
-    const bool any_bad = __builtin_amdgcn_ballot_w64(bad) != 0;
-    if (lane == 0) out[b] = any_bad ? __builtin_nanf("") : (float)(acc - logZ64[b]);
+    const bool wave_bad = __builtin_amdgcn_ballot_w64(bad) != 0;
+    if (lane == 0) {
+        part[wave] = acc;
+        part_bad[wave] = wave_bad ? 1 : 0;
+    }
+    __syncthreads();
+    if (tid == 0) {
+        double total = 0.0;
+        int any_bad = 0;
+        for (int w = 0; w < kPathThreads / 64; ++w) {
+            total += part[w];
+            any_bad |= part_bad[w];
+        }
+        out[b] = any_bad ? __builtin_nanf("") : (float)(total - logZ64[b]);
+    }
 }
 
 hipError_t launch_path_log_prob(int dtype, const void* phi, const int32_t* lengths, const int32_t* tags, int B, int N,
                                 int T, const double* logZ64, float* out, hipStream_t st) {
     if (dtype == 0)
-        hipLaunchKernelGGL(path_log_prob_kernel<float>, dim3(B), dim3(64), 0, st, static_cast<const float*>(phi), lengths,
+        hipLaunchKernelGGL(path_log_prob_kernel<float>, dim3(B), dim3(kPathThreads), 0, st, static_cast<const float*>(phi), lengths,
                            tags, N, T, logZ64, out);
     else
-        hipLaunchKernelGGL(path_log_prob_kernel<uint16_t>, dim3(B), dim3(64), 0, st, static_cast<const uint16_t*>(phi),
+        hipLaunchKernelGGL(path_log_prob_kernel<uint16_t>, dim3(B), dim3(kPathThreads), 0, st, static_cast<const uint16_t*>(phi),
                            lengths, tags, N, T, logZ64, out);
     return hipGetLastError();
 }
