@@ -126,7 +126,7 @@ __device__ __forceinline__ void fwd_fast(ChainSmem<G>& sm, int buf, int flag, in
             e[j] = ex2(__builtin_fmaf(v[k][j], kLog2e, uac));
             ls[j] += e[j];
         }
-        if (WITH_MU) store4<ALIGNED>(mu_out, T, r0 + k * G::RPP, c4, e[0] * gm[0], e[1] * gm[1], e[2] * gm[2], e[3] * gm[3]);
+        if (WITH_MU) store4<ALIGNED, (G::TCAP > 64)>(mu_out, T, r0 + k * G::RPP, c4, e[0] * gm[0], e[1] * gm[1], e[2] * gm[2], e[3] * gm[3]);
     }
     if (WITH_MU) {
         float tot = (ls[0] * gm[0] + ls[1] * gm[1]) + (ls[2] * gm[2] + ls[3] * gm[3]);
@@ -189,7 +189,7 @@ __device__ __forceinline__ void fwd_exact(ChainSmem<G>& sm, int buf, int tid, in
             e[j] = ex2(x[k][j] - g[j]);
             ls[j] += e[j];
         }
-        if (WITH_MU) store4<ALIGNED>(mu_out, T, r0 + k * G::RPP, c4, e[0] * gm[0], e[1] * gm[1], e[2] * gm[2], e[3] * gm[3]);
+        if (WITH_MU) store4<ALIGNED, (G::TCAP > 64)>(mu_out, T, r0 + k * G::RPP, c4, e[0] * gm[0], e[1] * gm[1], e[2] * gm[2], e[3] * gm[3]);
     }
     if (WITH_MU) {
         float tot = (ls[0] * gm[0] + ls[1] * gm[1]) + (ls[2] * gm[2] + ls[3] * gm[3]);
@@ -248,7 +248,7 @@ __device__ __forceinline__ void bwd_fast(ChainSmem<G>& sm, int buf, int flag, in
         S[k] = (e[0] + e[1]) + (e[2] + e[3]);
         if (WITH_MU) {
             const float f = ex2(c + uaK[k]);
-            store4<ALIGNED>(mu_out, T, r0 + k * G::RPP, c4, e[0] * f, e[1] * f, e[2] * f, e[3] * f);
+            store4<ALIGNED, (G::TCAP > 64)>(mu_out, T, r0 + k * G::RPP, c4, e[0] * f, e[1] * f, e[2] * f, e[3] * f);
             tot += S[k] * f;
         }
     }
@@ -317,7 +317,7 @@ __device__ __forceinline__ void bwd_exact(ChainSmem<G>& sm, int buf, int tid, in
         S[k] = (e[0] + e[1]) + (e[2] + e[3]);
         if (WITH_MU) {
             const float f = ex2(g + uaK[k]);
-            store4<ALIGNED>(mu_out, T, r0 + k * G::RPP, c4, e[0] * f, e[1] * f, e[2] * f, e[3] * f);
+            store4<ALIGNED, (G::TCAP > 64)>(mu_out, T, r0 + k * G::RPP, c4, e[0] * f, e[1] * f, e[2] * f, e[3] * f);
             tot += S[k] * f;
         }
     }

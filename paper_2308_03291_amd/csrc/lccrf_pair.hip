@@ -30,6 +30,7 @@
 
 namespace lccrf {
 
+
 constexpr int kPairW = 512;        // threads that load and compute (8 waves)
 constexpr int kPairWaves = 8;
 constexpr int kPairThreads = kPairW + 64;  // plus one wave that only receives the partner's half
@@ -237,7 +238,7 @@ __global__ __launch_bounds__(kPairThreads) void pair_marginal_kernel(PairArgs a)
         auto load = [&](int i, int slot) {
 #pragma unroll
             for (int k = 0; k < ITEMS; ++k)
-                Elem<TIN>::get4(phib + (size_t)i * TT + (size_t)(r0 + k * RPP) * T + c4, ring[slot][k]);
+                Elem<TIN>::get4_stream(phib + (size_t)i * TT + (size_t)(r0 + k * RPP) * T + c4, ring[slot][k]);
             const float4 q = *reinterpret_cast<const float4*>(a.ub + (vb + i) * T + c4);
             aux[slot][0] = q.x; aux[slot][1] = q.y; aux[slot][2] = q.z; aux[slot][3] = q.w;
             off[slot] = a.Ob[vb + i];
@@ -270,8 +271,7 @@ __global__ __launch_bounds__(kPairThreads) void pair_marginal_kernel(PairArgs a)
                         e[j] = ex2(__builtin_fmaf(ring[slot][k][j], kLog2e, uac[k]));
                         ls[j] += e[j];
                     }
-                    *reinterpret_cast<float4*>(mrow + (size_t)(r0 + k * RPP) * T) =
-                        make_float4(e[0] * gm[0], e[1] * gm[1], e[2] * gm[2], e[3] * gm[3]);
+                    stream_store4(mrow + (size_t)(r0 + k * RPP) * T, e[0] * gm[0], e[1] * gm[1], e[2] * gm[2], e[3] * gm[3]);
                 }
                 {   // refill this slot with the tile kPairPF positions ahead (clamped: always issued)
                     const int ahead = done + kPairPF;
@@ -329,7 +329,7 @@ __global__ __launch_bounds__(kPairThreads) void pair_marginal_kernel(PairArgs a)
         auto load = [&](int i, int slot) {
 #pragma unroll
             for (int k = 0; k < ITEMS; ++k) {
-                Elem<TIN>::get4(phib + (size_t)i * TT + (size_t)(r0 + k * RPP) * T + c4, ring[slot][k]);
+                Elem<TIN>::get4_stream(phib + (size_t)i * TT + (size_t)(r0 + k * RPP) * T + c4, ring[slot][k]);
                 aux[slot][k] = a.ua[(vb + i - 1) * T + r0 + k * RPP];
             }
             off[slot] = a.Oa[vb + i - 1];
@@ -360,8 +360,7 @@ __global__ __launch_bounds__(kPairThreads) void pair_marginal_kernel(PairArgs a)
                     for (int j = 0; j < 4; ++j) e[j] = ex2(__builtin_fmaf(ring[slot][k][j], kLog2e, ubc[j]));
                     S[k] = (e[0] + e[1]) + (e[2] + e[3]);
                     const float f = ex2(d + aux[slot][k] + K);
-                    *reinterpret_cast<float4*>(mrow + (size_t)(r0 + k * RPP) * T) =
-                        make_float4(e[0] * f, e[1] * f, e[2] * f, e[3] * f);
+                    stream_store4(mrow + (size_t)(r0 + k * RPP) * T, e[0] * f, e[1] * f, e[2] * f, e[3] * f);
                     tl += S[k] * f;
                 }
                 {
