@@ -177,6 +177,28 @@ int lccrf_log_prob(const void* phi, lccrf_dtype dt, const int32_t* lengths, cons
 int lccrf_entropy(const void* phi, lccrf_dtype dt, const int32_t* lengths, int B, int N, int T,
                   float* entropy, void* workspace, size_t workspace_bytes, void* stream);
 
+/*
+ * The three queries from STRUCTURED potentials: phi[b][i][s][t] = trans[s][t] + emit[b][i][t], the
+ * usual tagging parameterisation (per-position emission scores plus one shared transition matrix;
+ * the paper's linear-chain CRF takes the dense per-position matrices these stand for, section
+ * "Sequence Tagging").  The dense tensor is never formed: the transition tile stays in registers
+ * and a position brings T numbers instead of T*T, so log-partition and argmax read T times less
+ * (marginals still write the dense [B,N,T,T] result).  Results equal those of the dense calls on
+ * the materialised phi up to rounding; the first tag is scored trans[0][t] + emit[b][0][t].
+ *   emit   [B][N][T] float32 (device), 16-byte aligned; trans [T][T] float32 (device), 16-byte aligned.
+ * T <= 64 (else LCCRF_ENOTIMPL).  Workspace: lccrf_workspace_bytes of the matching op with LCCRF_F32.
+ * Other arguments, outputs and errors as the dense calls.
+ */
+int lccrf_log_partition_structured(const float* emit, const float* trans, const int32_t* lengths,
+                                   int B, int N, int T, float* logZ,
+                                   void* workspace, size_t workspace_bytes, void* stream);
+int lccrf_marginals_structured(const float* emit, const float* trans, const int32_t* lengths,
+                               int B, int N, int T, float* logZ, float* marginals,
+                               void* workspace, size_t workspace_bytes, void* stream);
+int lccrf_argmax_structured(const float* emit, const float* trans, const int32_t* lengths,
+                            int B, int N, int T, float* best_score, int32_t* tags,
+                            void* workspace, size_t workspace_bytes, void* stream);
+
 /* Positions per chunk of LCCRF_ALGO_SCAN: a process-wide tuning knob (default 64; 0 restores the
  * default; values outside [4, 4096] return LCCRF_EINVAL and change nothing).  It enters
  * lccrf_workspace_bytes, so set it before sizing a workspace, and not while another thread is

@@ -30,7 +30,8 @@ MAX_T = 256
 EXPORTS = (
     "lccrf_workspace_bytes", "lccrf_log_partition", "lccrf_marginals", "lccrf_argmax",
     "lccrf_log_partition_algo", "lccrf_marginals_algo", "lccrf_argmax_algo",
-    "lccrf_marginals_timed", "lccrf_log_prob", "lccrf_entropy", "lccrf_set_scan_chunk", "lccrf_strerror",
+    "lccrf_marginals_timed", "lccrf_log_prob", "lccrf_entropy", "lccrf_log_partition_structured",
+    "lccrf_marginals_structured", "lccrf_argmax_structured", "lccrf_set_scan_chunk", "lccrf_strerror",
     "lccrf_version",
 )
 
@@ -72,6 +73,12 @@ def load_library() -> ctypes.CDLL:
     lib.lccrf_log_prob.restype = i
     lib.lccrf_entropy.argtypes = base + [vp, vp, sz, vp]
     lib.lccrf_entropy.restype = i
+    sbase = [vp, vp, vp, i, i, i]
+    lib.lccrf_log_partition_structured.argtypes = sbase + [vp, vp, sz, vp]
+    lib.lccrf_marginals_structured.argtypes = sbase + [vp, vp, vp, sz, vp]
+    lib.lccrf_argmax_structured.argtypes = sbase + [vp, vp, vp, sz, vp]
+    for n in ("lccrf_log_partition_structured", "lccrf_marginals_structured", "lccrf_argmax_structured"):
+        getattr(lib, n).restype = i
     lib.lccrf_set_scan_chunk.argtypes = [i]
     lib.lccrf_set_scan_chunk.restype = i
     _lib = lib
@@ -221,6 +228,69 @@ def lccrf_entropy(phi: torch.Tensor, lengths: Optional[torch.Tensor] = None, *,
                                out.data_ptr(), ws.data_ptr(), nws, _stream(phi.device))
     _check(rc, "lccrf_entropy")
     return out
+
+
+def _structured_args(emit: torch.Tensor, trans: torch.Tensor):
+    if emit.dtype != torch.float32 or trans.dtype != torch.float32 or emit.dim() != 3 or trans.dim() != 2:
+        raise LccrfError("emit must be float32 [B, N, T] and trans float32 [T, T]")
+    B, N, T = emit.shape
+    if tuple(trans.shape) != (T, T) or not emit.is_contiguous() or not trans.is_contiguous() or not emit.is_cuda \
+            or trans.device != emit.device:
+        raise LccrfError("emit [B, N, T] and trans [T, T] must be contiguous tensors on one GPU")
+    return B, N, T
+
+
+def lccrf_log_partition_structured(emit: torch.Tensor, trans: torch.Tensor, lengths: Optional[torch.Tensor] = None, *,
+                                   out: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None):
+    """logZ [B] of the chains with potentials trans[s, t] + emit[b, i, t] (never materialised)."""
+    lib = load_library()
+    B, N, T = _structured_args(emit, trans)
+    ws, nws = _workspace(OP_LOGZ, B, N, T, LCCRF_F32, emit.device, workspace)
+    if out is None:
+        out = torch.empty(B, dtype=torch.float32, device=emit.device)
+    with torch.cuda.device(emit.device):
+        rc = lib.lccrf_log_partition_structured(emit.data_ptr(), trans.data_ptr(), _len_ptr(lengths, B, emit.device),
+                                                B, N, T, out.data_ptr(), ws.data_ptr(), nws, _stream(emit.device))
+    _check(rc, "lccrf_log_partition_structured")
+    return out
+
+
+def lccrf_marginals_structured(emit: torch.Tensor, trans: torch.Tensor, lengths: Optional[torch.Tensor] = None, *,
+                               out: Optional[torch.Tensor] = None, logZ: Optional[torch.Tensor] = None,
+                               workspace: Optional[torch.Tensor] = None):
+    """(logZ [B], marginals [B, N, T, T]) for potentials trans[s, t] + emit[b, i, t]."""
+    lib = load_library()
+    B, N, T = _structured_args(emit, trans)
+    ws, nws = _workspace(OP_MARGINALS, B, N, T, LCCRF_F32, emit.device, workspace)
+    if out is None:
+        out = torch.empty(B, N, T, T, dtype=torch.float32, device=emit.device)
+    if logZ is None:
+        logZ = torch.empty(B, dtype=torch.float32, device=emit.device)
+    with torch.cuda.device(emit.device):
+        rc = lib.lccrf_marginals_structured(emit.data_ptr(), trans.data_ptr(), _len_ptr(lengths, B, emit.device),
+                                            B, N, T, logZ.data_ptr(), out.data_ptr(), ws.data_ptr(), nws,
+                                            _stream(emit.device))
+    _check(rc, "lccrf_marginals_structured")
+    return logZ, out
+
+
+def lccrf_argmax_structured(emit: torch.Tensor, trans: torch.Tensor, lengths: Optional[torch.Tensor] = None, *,
+                            out: Optional[torch.Tensor] = None, score: Optional[torch.Tensor] = None,
+                            workspace: Optional[torch.Tensor] = None):
+    """(best_score [B], tags [B, N]) for potentials trans[s, t] + emit[b, i, t]."""
+    lib = load_library()
+    B, N, T = _structured_args(emit, trans)
+    ws, nws = _workspace(OP_ARGMAX, B, N, T, LCCRF_F32, emit.device, workspace)
+    if out is None:
+        out = torch.empty(B, N, dtype=torch.int32, device=emit.device)
+    if score is None:
+        score = torch.empty(B, dtype=torch.float32, device=emit.device)
+    with torch.cuda.device(emit.device):
+        rc = lib.lccrf_argmax_structured(emit.data_ptr(), trans.data_ptr(), _len_ptr(lengths, B, emit.device),
+                                         B, N, T, score.data_ptr(), out.data_ptr(), ws.data_ptr(), nws,
+                                         _stream(emit.device))
+    _check(rc, "lccrf_argmax_structured")
+    return score, out
 
 
 def lccrf_marginals_timed(phi: torch.Tensor, lengths: Optional[torch.Tensor], out: torch.Tensor,

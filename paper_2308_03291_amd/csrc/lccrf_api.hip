@@ -253,6 +253,62 @@ int lccrf_entropy(const void* phi, lccrf_dtype dt, const int32_t* lengths, int B
     return e == hipSuccess ? LCCRF_OK : LCCRF_ELAUNCH;
 }
 
+// Common checks of the structured calls.
+static int check_structured(const float* emit, const float* trans, const int32_t* lengths, int B, int N, int T,
+                            const void* ws, size_t ws_bytes, size_t need) {
+    if (!shape_ok(B, N, T)) return LCCRF_EINVAL;
+    if (!emit || !trans) return LCCRF_ENULL;
+    if (!ws || ws_bytes < need) return LCCRF_EWORKSPACE;
+    if (!aligned_to(emit, 16) || !aligned_to(trans, 16) || !aligned_to(ws, kAlign)) return LCCRF_EALIGN;
+    if (lengths && !aligned_to(lengths, 4)) return LCCRF_EALIGN;
+    if (!lccrf::structured_supported(T)) return LCCRF_ENOTIMPL;
+    return LCCRF_OK;
+}
+
+static int structured_sum(int op, const float* emit, const float* trans, const int32_t* lengths, int B, int N, int T,
+                          float* logZ, float* marginals, void* workspace, size_t workspace_bytes, void* stream) {
+    const size_t need = lccrf_workspace_bytes(op == 0 ? LCCRF_OP_LOGZ : LCCRF_OP_MARGINALS, B, N, T, LCCRF_F32);
+    const int rc = check_structured(emit, trans, lengths, B, N, T, workspace, workspace_bytes, need);
+    if (rc != LCCRF_OK) return rc;
+    if (op == 0 && !logZ) return LCCRF_ENULL;
+    if (op == 1 && !marginals) return LCCRF_ENULL;
+    if ((logZ && !aligned_to(logZ, 4)) || (marginals && !aligned_to(marginals, 16))) return LCCRF_EALIGN;
+    const SumWorkspace w = sum_workspace(B, N, T);
+    char* base = static_cast<char*>(workspace);
+    const hipError_t e = lccrf::launch_sequential_sum(
+        op, LCCRF_F32, nullptr, lengths, B, N, T, reinterpret_cast<float*>(base + w.ua),
+        reinterpret_cast<float*>(base + w.ub), reinterpret_cast<double*>(base + w.Oa),
+        reinterpret_cast<double*>(base + w.Ob), logZ, marginals, static_cast<hipStream_t>(stream), nullptr, false,
+        nullptr, nullptr, nullptr, emit, trans);
+    return e == hipSuccess ? LCCRF_OK : LCCRF_ELAUNCH;
+}
+
+int lccrf_log_partition_structured(const float* emit, const float* trans, const int32_t* lengths, int B, int N, int T,
+                                   float* logZ, void* workspace, size_t workspace_bytes, void* stream) {
+    return structured_sum(0, emit, trans, lengths, B, N, T, logZ, nullptr, workspace, workspace_bytes, stream);
+}
+
+int lccrf_marginals_structured(const float* emit, const float* trans, const int32_t* lengths, int B, int N, int T,
+                               float* logZ, float* marginals, void* workspace, size_t workspace_bytes, void* stream) {
+    return structured_sum(1, emit, trans, lengths, B, N, T, logZ, marginals, workspace, workspace_bytes, stream);
+}
+
+int lccrf_argmax_structured(const float* emit, const float* trans, const int32_t* lengths, int B, int N, int T,
+                            float* best_score, int32_t* tags, void* workspace, size_t workspace_bytes, void* stream) {
+    const size_t need = lccrf_workspace_bytes(LCCRF_OP_ARGMAX, B, N, T, LCCRF_F32);
+    const int rc = check_structured(emit, trans, lengths, B, N, T, workspace, workspace_bytes, need);
+    if (rc != LCCRF_OK) return rc;
+    if (!tags) return LCCRF_ENULL;
+    if (!aligned_to(tags, 4) || (best_score && !aligned_to(best_score, 4))) return LCCRF_EALIGN;
+    const MaxWorkspace w = max_workspace(B, N, T);
+    char* base = static_cast<char*>(workspace);
+    const hipError_t e = lccrf::launch_structured_max(emit, trans, lengths, B, N, T,
+                                                      reinterpret_cast<uint8_t*>(base + w.bp),
+                                                      reinterpret_cast<double*>(base + w.mid), best_score, tags,
+                                                      static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? LCCRF_OK : LCCRF_ELAUNCH;
+}
+
 const char* lccrf_strerror(int code) {
     switch (code) {
         case LCCRF_OK: return "ok";
@@ -273,6 +329,6 @@ int lccrf_set_scan_chunk(int chunk) {
     return LCCRF_OK;
 }
 
-int lccrf_version(void) { return 102; }
+int lccrf_version(void) { return 103; }
 
 }  // extern "C"

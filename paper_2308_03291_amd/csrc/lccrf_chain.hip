@@ -549,15 +549,36 @@ __global__ __launch_bounds__(G::W) void chain_half_kernel(ChainArgs a) {
     for (int k = 0; k < ITEMS; ++k) dummyI[k] = 0.f;
     double O = 0.0;
     int buf = 0, nstep = 0;
-    auto load = [&](int i, int slot) { load_tile<G, TIN, ALIGNED>(phib + (size_t)i * TT, T, c4, r0, ring[slot]); };
+    // structured potentials (trans tile in registers, emissions streamed): geometries up to T = 64 only
+    constexpr bool CAN_STRUCT = G::TCAP <= 64;
+    const bool structured = CAN_STRUCT && a.emit != nullptr;
+    const float* emb = structured ? a.emit + (size_t)b * N * T : nullptr;
+    float tr[CAN_STRUCT ? ITEMS : 1][4];
+    if constexpr (CAN_STRUCT) {
+        if (structured) load_tile<G, float, ALIGNED>(a.trans, T, c4, r0, tr);
+    }
+    auto load = [&](int i, int slot) {
+        if constexpr (CAN_STRUCT) {
+            if (structured) { load_emit4<ALIGNED>(emb + (size_t)i * T, T, c4, ring[slot][0]); return; }
+        }
+        load_tile<G, TIN, ALIGNED>(phib + (size_t)i * TT, T, c4, r0, ring[slot]);
+    };
+    auto tile_ready = [&](int slot) {  // turns a slot that holds emissions into the tile
+        if constexpr (CAN_STRUCT) {
+            if (structured) add_trans<ITEMS>(ring[slot], tr);
+        }
+    };
 
     if (dir == 0) {
         float v0 = LCCRF_NEG_INF;
-        if (tid < T) v0 = sp.first ? Elem<TIN>::get(phib + tid) * kLog2e : a.Fv[((size_t)b * a.C + sp.c - 1) * T + tid];
+        if (tid < T)
+            v0 = !sp.first ? a.Fv[((size_t)b * a.C + sp.c - 1) * T + tid]
+                 : (structured ? a.trans[tid] + emb[tid] : Elem<TIN>::get(phib + tid)) * kLog2e;
         if (!sp.first) O = a.OF[(size_t)b * a.C + sp.c - 1];
         publish_columns<G>(sm, 0, tid, v0);
         __syncthreads();
         walk<PF>(p0 + 1, h, +1, load, [&](int i, int slot) {
+            tile_ready(slot);
             const float d = read_shift<G>(sm, buf);
             O += (double)d;
             float ua[ITEMS];
@@ -581,6 +602,7 @@ __global__ __launch_bounds__(G::W) void chain_half_kernel(ChainArgs a) {
         publish_columns<G>(sm, 0, tid, v0);
         __syncthreads();
         walk<PF>(e, h + 1, -1, load, [&](int i, int slot) {
+            tile_ready(slot);
             const float d = read_shift<G>(sm, buf);
             O += (double)d;
             const float4 q = *reinterpret_cast<const float4*>(&sm.rvec[buf][c4]);
@@ -670,6 +692,24 @@ __global__ __launch_bounds__(G::W) void chain_marginal_kernel(ChainArgs a) {
     float ring[PF][ITEMS][4];
     int buf = 0, nstep = 0;
     float kappa = 0.f;  // running correction that keeps each position's marginals summing to one
+    constexpr bool CAN_STRUCT = G::TCAP <= 64;
+    const bool structured = CAN_STRUCT && a.emit != nullptr;
+    const float* emb = structured ? a.emit + (size_t)b * N * T : nullptr;
+    float tr[CAN_STRUCT ? ITEMS : 1][4];
+    if constexpr (CAN_STRUCT) {
+        if (structured) load_tile<G, float, ALIGNED>(a.trans, T, c4, r0, tr);
+    }
+    auto load_phi = [&](int i, int slot) {
+        if constexpr (CAN_STRUCT) {
+            if (structured) { load_emit4<ALIGNED>(emb + (size_t)i * T, T, c4, ring[slot][0]); return; }
+        }
+        load_tile<G, TIN, ALIGNED>(phib + (size_t)i * TT, T, c4, r0, ring[slot]);
+    };
+    auto tile_ready = [&](int slot) {
+        if constexpr (CAN_STRUCT) {
+            if (structured) add_trans<ITEMS>(ring[slot], tr);
+        }
+    };
 
     if (dir == 0) {
         double O = a.Oa[vb + h];
@@ -678,12 +718,13 @@ __global__ __launch_bounds__(G::W) void chain_marginal_kernel(ChainArgs a) {
         float aux[PF][4];
         double ob[PF];
         auto load = [&](int i, int slot) {
-            load_tile<G, TIN, ALIGNED>(phib + (size_t)i * TT, T, c4, r0, ring[slot]);
+            load_phi(i, slot);
 #pragma unroll
             for (int j = 0; j < 4; ++j) aux[slot][j] = a.ub[(vb + i) * T + (c4 + j < T ? c4 + j : T - 1)];
             ob[slot] = a.Ob[vb + i];
         };
         walk<PF>(h + 1, e, +1, load, [&](int i, int slot) {
+            tile_ready(slot);
             const float d = read_shift<G>(sm, buf);
             kappa += read_drift<G>(sm, buf);
             O += (double)d;
@@ -707,7 +748,7 @@ __global__ __launch_bounds__(G::W) void chain_marginal_kernel(ChainArgs a) {
         float aux[PF][ITEMS];
         double oa[PF];
         auto load = [&](int i, int slot) {
-            load_tile<G, TIN, ALIGNED>(phib + (size_t)i * TT, T, c4, r0, ring[slot]);
+            load_phi(i, slot);
 #pragma unroll
             for (int k = 0; k < ITEMS; ++k) {
                 const int s = r0 + k * G::RPP;
@@ -716,6 +757,7 @@ __global__ __launch_bounds__(G::W) void chain_marginal_kernel(ChainArgs a) {
             oa[slot] = a.Oa[vb + i - 1];
         };
         walk<PF>(h, p0 + 1, -1, load, [&](int i, int slot) {
+            tile_ready(slot);
             const float d = read_shift<G>(sm, buf);
             kappa += read_drift<G>(sm, buf);
             O += (double)d;
@@ -835,13 +877,18 @@ static hipError_t launch_wave(int op, int dtype, const ChainArgs& a, hipStream_t
     return launch_wave_pass(true, dtype, a, st);
 }
 
+bool structured_supported(int T) { return T >= 1 && T <= 64; }
+
 // op: 0 = logZ only, 1 = marginals (+ logZ).  Workspace pointers already carved by the caller.
 hipError_t launch_sequential_sum(int op, int dtype, const void* phi, const int32_t* lengths, int B, int N, int T,
                                  float* ua, float* ub, double* Oa, double* Ob, float* logZ, float* mu,
                                  hipStream_t st, hipEvent_t between, bool exact_only, unsigned long long* mail,
-                                 int* failed, double* logZ64) {
+                                 int* failed, double* logZ64, const float* emit, const float* trans) {
     ChainArgs a{phi, lengths, B, N, T, ua, ub, Oa, Ob, logZ, mu, exact_only ? 1 : 0, nullptr, 0, 1, nullptr, nullptr, nullptr, nullptr};
     a.logZ64 = logZ64;
+    a.emit = emit;
+    a.trans = trans;
+    if (emit && T > 64) return hipErrorInvalidValue;  // the caller checks structured_supported(T) first
     if (wave_supported(T)) return launch_wave(op, dtype, a, st, between);
     // Pairs pay off when one workgroup per chain would leave at least half of the chip idle.
     static const int cus = [] {

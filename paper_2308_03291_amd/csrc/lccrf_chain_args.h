@@ -36,6 +36,10 @@ struct ChainArgs {
     // the path behind them given the current tag, and leave it here for the meeting position.
     float* ha;  // [B][T] H(y_0 .. y_{h-1} | y_h = t), base-2
     float* hb;  // [B][T] H(y_{h+1} .. y_{L-1} | y_h = t), base-2
+    // Structured potentials (emit non-null; float only, T <= 64, whole sequences): phi is not read,
+    // phi[b][i][s][t] = trans[s][t] + emit[b][i][t].
+    const float* emit;   // [B][N][T]
+    const float* trans;  // [T][T]
 };
 
 // The stretch of positions one pair of workgroups handles: all of a sequence, or one chunk.

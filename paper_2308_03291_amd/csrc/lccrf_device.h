@@ -108,6 +108,29 @@ __device__ __forceinline__ void load_tile(const TIN* __restrict__ mat, int T, in
     }
 }
 
+// Structured potentials phi[i][s][t] = trans[s][t] + emit[i][t] (the usual tagging parameterisation;
+// the dense layout of the paper's linear-chain CRF with the per-position part factored out): the
+// transition tile stays in registers (loaded once with load_tile / wave_load), a position brings
+// only its T emission scores.  load_emit4 puts this thread's four columns into row 0 of the slot;
+// add_trans then turns the slot into the tile of that position.
+template <bool ALIGNED>
+__device__ __forceinline__ void load_emit4(const float* __restrict__ emit_row, int T, int c4, float (&o)[4]) {
+    if (ALIGNED) {
+        Elem<float>::get4(emit_row + (c4 < T ? c4 : T - 4), o);
+    } else {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) o[j] = emit_row[c4 + j < T ? c4 + j : T - 1];
+    }
+}
+template <int ROWS>
+__device__ __forceinline__ void add_trans(float (&v)[ROWS][4], const float (&tr)[ROWS][4]) {
+    const float em[4] = {v[0][0], v[0][1], v[0][2], v[0][3]};
+#pragma unroll
+    for (int k = 0; k < ROWS; ++k)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) v[k][j] = tr[k][j] + em[j];
+}
+
 // Replace the entries of a loaded tile that lie outside the T x T matrix by -inf, the
 // neutral element of both max and log-sum-exp.
 template <typename G>

@@ -17,7 +17,10 @@ namespace lccrf {
 hipError_t launch_sequential_sum(int op, int dtype, const void* phi, const int32_t* lengths, int B, int N, int T,
                                  float* ua, float* ub, double* Oa, double* Ob, float* logZ, float* mu,
                                  hipStream_t st, hipEvent_t between = nullptr, bool exact_only = false,
-                                 unsigned long long* mail = nullptr, int* failed = nullptr, double* logZ64 = nullptr);
+                                 unsigned long long* mail = nullptr, int* failed = nullptr, double* logZ64 = nullptr,
+                                 const float* emit = nullptr, const float* trans = nullptr);
+// Structured potentials (emit [B][N][T] + trans [T][T], float, phi unused) are served for these T.
+bool structured_supported(int T);
 
 // Paired second pass (two workgroups per chain; lccrf_pair.hip).
 size_t pair_mail_words(int B);
@@ -49,6 +52,9 @@ hipError_t launch_chunked_marginals(int dtype, const void* phi, const int32_t* l
 // mid: viterbi_mid_doubles(B, 1, T) doubles of scratch.
 size_t viterbi_mid_doubles(int B, int C, int T);
 hipError_t launch_sequential_max(int dtype, const void* phi, const int32_t* lengths, int B, int N, int T,
+                                 uint8_t* bp, double* mid, float* best_score, int32_t* tags, hipStream_t st);
+
+hipError_t launch_structured_max(const float* emit, const float* trans, const int32_t* lengths, int B, int N, int T,
                                  uint8_t* bp, double* mid, float* best_score, int32_t* tags, hipStream_t st);
 
 // Max-plus chunked scan (lccrf_scan.hip): the best score and the tag of the best path at the last

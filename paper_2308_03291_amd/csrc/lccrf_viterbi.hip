@@ -60,6 +60,9 @@ struct VitArgs {
     // lccrf_scan.hip); the best score is the scan's and is not written here.
     int chunk, C;
     const int32_t* pin;  // [B][C] tag at the last position of each chunk
+    // Structured potentials (emit non-null; float, T <= 64): phi[b][i][s][t] = trans[s][t] + emit[b][i][t].
+    const float* emit;   // [B][N][T]
+    const float* trans;  // [T][T]
 };
 
 // The stretch of positions one pair of workgroups handles.
@@ -103,9 +106,16 @@ __global__ __launch_bounds__(G::W) void viterbi_half_kernel(VitArgs a) {
 
     for (int k = tid; k < 2 * G::TCAP; k += G::W) (&sm.dvec[0][0])[k] = ninf;
     __syncthreads();
+    constexpr bool CAN_STRUCT = G::TCAP <= 64;
+    const bool structured = CAN_STRUCT && a.emit != nullptr;
+    const float* emb = structured ? a.emit + (size_t)b * N * T : nullptr;
+    float tr[CAN_STRUCT ? ITEMS : 1][4];
+    if constexpr (CAN_STRUCT) {
+        if (structured) load_tile<G, float, ALIGNED>(a.trans, T, c4, r0, tr);
+    }
     if (tid < T) {
         if (dir == 0) {
-            if (sp.t0 == 0) sm.dvec[0][tid] = (double)Elem<TIN>::get(phib + tid);
+            if (sp.t0 == 0) sm.dvec[0][tid] = structured ? (double)(a.trans[tid] + emb[tid]) : (double)Elem<TIN>::get(phib + tid);
             else sm.dvec[0][tid] = (tid == a.pin[(size_t)b * a.C + sp.c - 1]) ? 0.0 : ninf;
         } else {
             // a whole sequence may end in any tag; a chunk must end in its pinned tag
@@ -117,8 +127,20 @@ __global__ __launch_bounds__(G::W) void viterbi_half_kernel(VitArgs a) {
     int buf = 0;
     float A[ITEMS][4], Bq[ITEMS][4];
     // forward: column maxima over rows, merged across waves through LDS
+    auto fetch = [&](int i, float (&v)[ITEMS][4]) {
+        if constexpr (CAN_STRUCT) {
+            if (structured) { load_emit4<ALIGNED>(emb + (size_t)i * T, T, c4, v[0]); return; }
+        }
+        load_tile<G, TIN, ALIGNED>(phib + (size_t)i * TT, T, c4, r0, v);
+    };
+    auto tile_ready = [&](float (&v)[ITEMS][4]) {
+        if constexpr (CAN_STRUCT) {
+            if (structured) add_trans<ITEMS>(v, tr);
+        }
+    };
     auto fwd_step = [&](int i, float (&v)[ITEMS][4]) {
       if constexpr (!TURNED) {
+        tile_ready(v);
         mask_tile<G>(v, T, c4, r0);
         double best[4] = {ninf, ninf, ninf, ninf};
         int arg[4] = {kNoArg, kNoArg, kNoArg, kNoArg};
@@ -163,6 +185,7 @@ __global__ __launch_bounds__(G::W) void viterbi_half_kernel(VitArgs a) {
     };
     // backward: row maxima over columns, inside the wave
     auto bwd_step = [&](int i, float (&v)[ITEMS][4]) {
+        tile_ready(v);
         mask_tile<G>(v, T, c4, r0);
         double ek[4];
 #pragma unroll
@@ -219,13 +242,13 @@ __global__ __launch_bounds__(G::W) void viterbi_half_kernel(VitArgs a) {
         const int n = (last - first) * step_dir + 1;
         if (n <= 0) return;
         int left = n;
-        load_tile<G, TIN, ALIGNED>(phib + (size_t)i * TT, T, c4, r0, A);
+        fetch(i, A);
         while (left > 0) {
-            if (left > 1) load_tile<G, TIN, ALIGNED>(phib + (size_t)(i + step_dir) * TT, T, c4, r0, Bq);
+            if (left > 1) fetch(i + step_dir, Bq);
             step(i, A);
             i += step_dir;
             if (--left == 0) break;
-            if (left > 1) load_tile<G, TIN, ALIGNED>(phib + (size_t)(i + step_dir) * TT, T, c4, r0, A);
+            if (left > 1) fetch(i + step_dir, A);
             step(i, Bq);
             i += step_dir;
             --left;
@@ -416,13 +439,20 @@ size_t viterbi_mid_doubles(int B, int C, int T) { return (size_t)B * C * 2 * T; 
 
 hipError_t launch_sequential_max(int dtype, const void* phi, const int32_t* lengths, int B, int N, int T,
                                  uint8_t* bp, double* mid, float* best_score, int32_t* tags, hipStream_t st) {
-    return launch_any(dtype, VitArgs{phi, lengths, B, N, T, bp, mid, best_score, tags, 0, 1, nullptr}, st);
+    return launch_any(dtype, VitArgs{phi, lengths, B, N, T, bp, mid, best_score, tags, 0, 1, nullptr, nullptr, nullptr}, st);
+}
+
+// The same from structured potentials (float emit [B][N][T] + trans [T][T]; T <= 64).
+hipError_t launch_structured_max(const float* emit, const float* trans, const int32_t* lengths, int B, int N, int T,
+                                 uint8_t* bp, double* mid, float* best_score, int32_t* tags, hipStream_t st) {
+    if (T > 64) return hipErrorInvalidValue;
+    return launch_any(0, VitArgs{nullptr, lengths, B, N, T, bp, mid, best_score, tags, 0, 1, nullptr, emit, trans}, st);
 }
 
 // Best path inside every chunk between the tags the max-plus scan has pinned at the chunk ends.
 hipError_t launch_chunked_max(int dtype, const void* phi, const int32_t* lengths, int B, int N, int T, uint8_t* bp,
                               double* mid, int32_t* tags, int chunk, const int32_t* pin, hipStream_t st) {
-    return launch_any(dtype, VitArgs{phi, lengths, B, N, T, bp, mid, nullptr, tags, chunk, (N + chunk - 1) / chunk, pin}, st);
+    return launch_any(dtype, VitArgs{phi, lengths, B, N, T, bp, mid, nullptr, tags, chunk, (N + chunk - 1) / chunk, pin, nullptr, nullptr}, st);
 }
 
 }  // namespace lccrf

@@ -84,6 +84,12 @@ __device__ __forceinline__ void wave_load(const TIN* __restrict__ mat, int T, in
     }
 }
 
+// The same lane's share of an emission row (row 0 of the slot) for structured potentials.
+template <int TP, bool ALIGNED>
+__device__ __forceinline__ void wave_load_emit(const float* __restrict__ emit_row, int T, int lane, float (&v)[WGeo<TP>::R][4]) {
+    load_emit4<ALIGNED>(emit_row, T, 4 * (lane % WGeo<TP>::CG), v[0]);
+}
+
 __device__ __forceinline__ float max4(const float (&x)[4]) { return fmaxf(fmaxf(x[0], x[1]), fmaxf(x[2], x[3])); }
 
 // One forward position: r(t) = log2 sum_s 2^(ua(s) + phi2(s,t)), ua in row form, r in column form.
@@ -264,7 +270,14 @@ __global__ __launch_bounds__(64) void wave_half_kernel(ChainArgs a) {
     const TIN* phib = static_cast<const TIN*>(a.phi) + (size_t)b * N * TT;
     const bool exact_only = a.exact_only != 0;
     float ring[PF][R][4];
-    auto load = [&](int i, int slot) { wave_load<TP, TIN, ALIGNED>(phib + (size_t)i * TT, T, lane, ring[slot]); };
+    const bool structured = a.emit != nullptr;
+    const float* emb = structured ? a.emit + (size_t)b * N * T : nullptr;
+    float tr[R][4];
+    if (structured) wave_load<TP, float, ALIGNED>(a.trans, T, lane, tr);
+    auto load = [&](int i, int slot) {
+        if (structured) wave_load_emit<TP, ALIGNED>(emb + (size_t)i * T, T, lane, ring[slot]);
+        else wave_load<TP, TIN, ALIGNED>(phib + (size_t)i * TT, T, lane, ring[slot]);
+    };
     const float none4[4] = {0.f, 0.f, 0.f, 0.f};
     float noneR[R];
 #pragma unroll
@@ -278,7 +291,9 @@ __global__ __launch_bounds__(64) void wave_half_kernel(ChainArgs a) {
         for (int j = 0; j < 4; ++j) {
             const int t = c4 + j;
             vc[j] = LCCRF_NEG_INF;
-            if (t < T) vc[j] = sp.first ? Elem<TIN>::get(phib + t) * kLog2e : a.Fv[((size_t)b * a.C + sp.c - 1) * T + t];
+            if (t < T)
+                vc[j] = !sp.first ? a.Fv[((size_t)b * a.C + sp.c - 1) * T + t]
+                        : (structured ? a.trans[t] + emb[t] : Elem<TIN>::get(phib + t)) * kLog2e;
         }
         if (!sp.first) O = a.OF[(size_t)b * a.C + sp.c - 1];
         auto settle = [&](int pos) {  // normalise the vector of position `pos` and store it
@@ -297,6 +312,7 @@ __global__ __launch_bounds__(64) void wave_half_kernel(ChainArgs a) {
         };
         float hc[4] = {0.f, 0.f, 0.f, 0.f};  // entropy of the path behind each tag, column form
         walk<PF>(p0 + 1, h, +1, load, [&](int i, int slot) {
+            if (structured) add_trans<R>(ring[slot], tr);
             const float d = settle(i - 1);
             float ua[R], hrow[R];
             col_to_row<TP>(vc, ua, lane);
@@ -339,6 +355,7 @@ __global__ __launch_bounds__(64) void wave_half_kernel(ChainArgs a) {
 #pragma unroll
         for (int k = 0; k < R; ++k) hr[k] = 0.f;
         walk<PF>(e, h + 1, -1, load, [&](int i, int slot) {
+            if (structured) add_trans<R>(ring[slot], tr);
             const float d = settle(i);
             float ub[4], hcol[4];
             row_to_col<TP>(vr, ub, lane);
@@ -407,6 +424,14 @@ __global__ __launch_bounds__(64) void wave_marginal_kernel(ChainArgs a) {
     if (dir == 0 && sp.c == 0 && lane == 0 && a.logZ) a.logZ[b] = (float)(lz2 * kLn2);
 
     float ring[PF][R][4];
+    const bool structured = a.emit != nullptr;
+    const float* emb = structured ? a.emit + (size_t)b * N * T : nullptr;
+    float tr[R][4];
+    if (structured) wave_load<TP, float, ALIGNED>(a.trans, T, lane, tr);
+    auto load_phi = [&](int i, int slot) {
+        if (structured) wave_load_emit<TP, ALIGNED>(emb + (size_t)i * T, T, lane, ring[slot]);
+        else wave_load<TP, TIN, ALIGNED>(phib + (size_t)i * TT, T, lane, ring[slot]);
+    };
     float kappa = 0.f, tot = 0.f;
     float noh_c[4] = {0.f, 0.f, 0.f, 0.f}, noh_r[R];  // no entropy carried in this pass
 #pragma unroll
@@ -420,12 +445,13 @@ __global__ __launch_bounds__(64) void wave_marginal_kernel(ChainArgs a) {
         float aux[PF][4];
         double ob[PF];
         auto load = [&](int i, int slot) {
-            wave_load<TP, TIN, ALIGNED>(phib + (size_t)i * TT, T, lane, ring[slot]);
+            load_phi(i, slot);
 #pragma unroll
             for (int j = 0; j < 4; ++j) aux[slot][j] = a.ub[(vb + i) * T + (c4 + j < T ? c4 + j : T - 1)];
             ob[slot] = a.Ob[vb + i];
         };
         walk<PF>(h + 1, e, +1, load, [&](int i, int slot) {
+            if (structured) add_trans<R>(ring[slot], tr);
             const float d = finite_or_zero(xor_max<1, W::CG>(max4(vc)));
             kappa += drift_of(tot);
             O += (double)d;
@@ -447,12 +473,13 @@ __global__ __launch_bounds__(64) void wave_marginal_kernel(ChainArgs a) {
         float aux[PF][R];
         double oa[PF];
         auto load = [&](int i, int slot) {
-            wave_load<TP, TIN, ALIGNED>(phib + (size_t)i * TT, T, lane, ring[slot]);
+            load_phi(i, slot);
 #pragma unroll
             for (int k = 0; k < R; ++k) aux[slot][k] = a.ua[(vb + i - 1) * T + (s0 + k < T ? s0 + k : T - 1)];
             oa[slot] = a.Oa[vb + i - 1];
         };
         walk<PF>(h, p0 + 1, -1, load, [&](int i, int slot) {
+            if (structured) add_trans<R>(ring[slot], tr);
             float m = vr[0];
 #pragma unroll
             for (int k = 1; k < R; ++k) m = fmaxf(m, vr[k]);

@@ -1,0 +1,99 @@
+"""GPU parity of the structured calls (emit [B,N,T] + trans [T,T]) against the CPU oracle run on the
+materialised dense potentials phi[b,i,s,t] = trans[s,t] + emit[b,i,t]: the definition of what
+the structured form stands for.  Tolerances as in test_gpu_parity.py."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2308_03291_amd import workloads
+from test_gpu_parity import check_case, crf, _close_logz, _path_score, LOGZ_RTOL, GAP_MIN  # noqa: F401
+
+pytestmark = pytest.mark.gpu
+
+
+def _make(seed, B, N, T, scale_e=2.0, scale_t=1.0):
+    g = torch.Generator().manual_seed(seed)
+    emit = torch.randn(B, N, T, generator=g) * scale_e
+    trans = torch.randn(T, T, generator=g) * scale_t
+    return emit.contiguous(), trans.contiguous()
+
+
+def _check(crf, oracle_mod, emit, trans, lens, what):
+    B, N, T = emit.shape
+    phi = (emit[:, :, None, :] + trans[None, None]).contiguous()   # the same float32 additions the kernels make
+    lens_np = None if lens is None else lens.numpy()
+    eff = np.full((B,), N) if lens is None else np.clip(lens_np, 0, N)
+    de, dtr = emit.cuda(), trans.cuda()
+    dl = None if lens is None else lens.cuda()
+
+    lz = crf.lccrf_log_partition_structured(de, dtr, dl).cpu().numpy()
+    want_lz, want_mu = oracle_mod.marginals(phi, lens_np)
+    _close_logz(lz, want_lz, what + " logZ")
+
+    lz2, mu = crf.lccrf_marginals_structured(de, dtr, dl)
+    _close_logz(lz2.cpu().numpy(), want_lz, what + " marginals.logZ")
+    got_mu = mu.cpu().numpy().astype(np.float64)
+    assert np.isfinite(got_mu).all()
+    assert np.abs(got_mu - want_mu).max() <= 1e-5, f"{what}: max |mu - oracle| = {np.abs(got_mu - want_mu).max():.3e}"
+    for b in range(B):
+        assert not got_mu[b, eff[b]:].any() and (eff[b] == 0 or not got_mu[b, 0, 1:].any())
+
+    score, tags = crf.lccrf_argmax_structured(de, dtr, dl)
+    want_score, want_tags, gap = oracle_mod.viterbi(phi, lens_np)
+    _close_logz(score.cpu().numpy(), want_score, what + " score")
+    tags = tags.cpu().numpy()
+    phi64 = phi.numpy().astype(np.float64)
+    for b in range(B):
+        L = int(eff[b])
+        assert (tags[b, L:] == -1).all()
+        y = tags[b, :L]
+        assert ((y >= 0) & (y < T)).all()
+        if gap[b] > GAP_MIN:
+            assert np.array_equal(y, want_tags[b, :L]), f"{what}: path differs in sequence {b}"
+        elif np.isfinite(want_score[b]):
+            assert abs(_path_score(phi64[b], y, L) - want_score[b]) <= LOGZ_RTOL * max(1.0, abs(want_score[b])) + GAP_MIN
+
+
+@pytest.mark.parametrize("T,N", [(1, 4), (2, 9), (5, 8), (9, 33), (16, 40), (17, 12), (32, 65), (33, 7), (45, 50), (48, 33),
+                                 (64, 20), (63, 5)])
+def test_structured_sweep(crf, oracle_mod, T, N):
+    emit, trans = _make(7000 + 17 * T + N, 5, N, T)
+    lens = torch.tensor([N, max(N - 1, 0), min(2, N), 1, 0], dtype=torch.int32)
+    _check(crf, oracle_mod, emit, trans, lens, f"structured T={T} N={N}")
+
+
+def test_structured_config3(crf, oracle_mod):
+    """Config 3 is exactly this structure (emissions of scale 2 plus one transition matrix)."""
+    w = workloads.WORKLOADS["cfg3"]
+    g = torch.Generator().manual_seed(33)
+    emit = (torch.randn(w.B, w.N, w.T, generator=g) * 2.0).contiguous()
+    trans = torch.randn(w.T, w.T, generator=g).contiguous()
+    _check(crf, oracle_mod, emit, trans, workloads.lengths(w), "structured cfg3 shape")
+
+
+def test_structured_with_forbidden_transitions(crf, oracle_mod):
+    """BIO-style constraints: -inf entries in the transition matrix."""
+    T, N = 9, 30
+    emit, trans = _make(7100, 4, N, T)
+    trans[0, 2] = trans[0, 4] = trans[1, 4] = trans[3, 2] = float("-inf")
+    trans[:, 8] = float("-inf")
+    trans[8, 8] = 0.0
+    _check(crf, oracle_mod, emit, trans, None, "structured with -inf")
+
+
+def test_structured_agrees_with_dense_call(crf):
+    emit, trans = _make(7200, 8, 100, 32)
+    phi = (emit[:, :, None, :] + trans[None, None]).contiguous().cuda()
+    lz_a, mu_a = crf.lccrf_marginals_structured(emit.cuda(), trans.cuda())
+    lz_b, mu_b = crf.lccrf_marginals(phi)
+    assert torch.allclose(lz_a, lz_b, rtol=1e-6, atol=0)
+    assert float((mu_a - mu_b).abs().max()) < 2e-6
+    s_a, y_a = crf.lccrf_argmax_structured(emit.cuda(), trans.cuda())
+    s_b, y_b = crf.lccrf_argmax(phi)
+    assert torch.equal(y_a, y_b) and torch.equal(s_a, s_b)
+
+
+def test_structured_needs_a_supported_tag_set(crf):
+    emit, trans = _make(7300, 2, 6, 65)
+    with pytest.raises(crf.LccrfError, match="not available"):
+        crf.lccrf_log_partition_structured(emit.cuda(), trans.cuda())
