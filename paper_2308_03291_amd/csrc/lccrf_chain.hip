@@ -511,7 +511,8 @@ __device__ __forceinline__ void forward_half_turned(ChainSmem<G>& sm, float* __r
 
 // ---------------------------------------------------------------------------------------
 // Pass 1: both half chains, vectors stored, nothing else written.
-template <typename G, typename TIN, bool ALIGNED, int PF>
+// STRUCT: potentials are trans + emit (float, T <= 64; a compile-time choice, see lccrf_wave.hip).
+template <typename G, typename TIN, bool ALIGNED, int PF, bool STRUCT = false>
 __global__ __launch_bounds__(G::W) void chain_half_kernel(ChainArgs a) {
     __shared__ ChainSmem<G> sm;
     constexpr int ITEMS = G::ITEMS;
@@ -550,22 +551,23 @@ __global__ __launch_bounds__(G::W) void chain_half_kernel(ChainArgs a) {
     double O = 0.0;
     int buf = 0, nstep = 0;
     // structured potentials (trans tile in registers, emissions streamed): geometries up to T = 64 only
-    constexpr bool CAN_STRUCT = G::TCAP <= 64;
-    const bool structured = CAN_STRUCT && a.emit != nullptr;
+    constexpr bool CAN_STRUCT = STRUCT;
+    constexpr bool structured = STRUCT;
     const float* emb = structured ? a.emit + (size_t)b * N * T : nullptr;
     float tr[CAN_STRUCT ? ITEMS : 1][4];
     if constexpr (CAN_STRUCT) {
-        if (structured) load_tile<G, float, ALIGNED>(a.trans, T, c4, r0, tr);
+        load_tile<G, float, ALIGNED>(a.trans, T, c4, r0, tr);
     }
     auto load = [&](int i, int slot) {
         if constexpr (CAN_STRUCT) {
-            if (structured) { load_emit4<ALIGNED>(emb + (size_t)i * T, T, c4, ring[slot][0]); return; }
+            load_emit4<ALIGNED>(emb + (size_t)i * T, T, c4, ring[slot][0]);
+            return;
         }
         load_tile<G, TIN, ALIGNED>(phib + (size_t)i * TT, T, c4, r0, ring[slot]);
     };
     auto tile_ready = [&](int slot) {  // turns a slot that holds emissions into the tile
         if constexpr (CAN_STRUCT) {
-            if (structured) add_trans<ITEMS>(ring[slot], tr);
+            add_trans<ITEMS>(ring[slot], tr);
         }
     };
 
@@ -646,7 +648,7 @@ __device__ __forceinline__ double midpoint_log2z(ChainSmem<G>& sm, const ChainAr
 
 // ---------------------------------------------------------------------------------------
 // Pass 2: both chains continue past the meeting point and write the marginals.
-template <typename G, typename TIN, bool ALIGNED, int PF>
+template <typename G, typename TIN, bool ALIGNED, int PF, bool STRUCT = false>
 __global__ __launch_bounds__(G::W) void chain_marginal_kernel(ChainArgs a) {
     __shared__ ChainSmem<G> sm;
     constexpr int ITEMS = G::ITEMS;
@@ -692,22 +694,23 @@ __global__ __launch_bounds__(G::W) void chain_marginal_kernel(ChainArgs a) {
     float ring[PF][ITEMS][4];
     int buf = 0, nstep = 0;
     float kappa = 0.f;  // running correction that keeps each position's marginals summing to one
-    constexpr bool CAN_STRUCT = G::TCAP <= 64;
-    const bool structured = CAN_STRUCT && a.emit != nullptr;
+    constexpr bool CAN_STRUCT = STRUCT;
+    constexpr bool structured = STRUCT;
     const float* emb = structured ? a.emit + (size_t)b * N * T : nullptr;
     float tr[CAN_STRUCT ? ITEMS : 1][4];
     if constexpr (CAN_STRUCT) {
-        if (structured) load_tile<G, float, ALIGNED>(a.trans, T, c4, r0, tr);
+        load_tile<G, float, ALIGNED>(a.trans, T, c4, r0, tr);
     }
     auto load_phi = [&](int i, int slot) {
         if constexpr (CAN_STRUCT) {
-            if (structured) { load_emit4<ALIGNED>(emb + (size_t)i * T, T, c4, ring[slot][0]); return; }
+            load_emit4<ALIGNED>(emb + (size_t)i * T, T, c4, ring[slot][0]);
+            return;
         }
         load_tile<G, TIN, ALIGNED>(phib + (size_t)i * TT, T, c4, r0, ring[slot]);
     };
     auto tile_ready = [&](int slot) {
         if constexpr (CAN_STRUCT) {
-            if (structured) add_trans<ITEMS>(ring[slot], tr);
+            add_trans<ITEMS>(ring[slot], tr);
         }
     };
 
@@ -854,6 +857,25 @@ static hipError_t launch_geo(int op, ChainArgs a, hipStream_t st, hipEvent_t bet
     return hipGetLastError();
 }
 
+// Structured potentials at 32 < T <= 64.
+template <bool ALIGNED>
+static hipError_t launch_structured_64(int op, const ChainArgs& a, hipStream_t st, hipEvent_t between) {
+    using G = Geo<16, 4, 4>;
+    hipLaunchKernelGGL((chain_half_kernel<G, float, ALIGNED, 4, true>), dim3(2 * a.B), dim3(G::W), 0, st, a);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    if (between) {
+        e = hipEventRecord(between, st);
+        if (e != hipSuccess) return e;
+    }
+    if (op == 0) {
+        hipLaunchKernelGGL(logz_combine_kernel, dim3(a.B), dim3(64), 0, st, a);
+        return hipGetLastError();
+    }
+    hipLaunchKernelGGL((chain_marginal_kernel<G, float, ALIGNED, 3, true>), dim3(2 * a.B), dim3(G::W), 0, st, a);
+    return hipGetLastError();
+}
+
 template <typename TIN, bool ALIGNED>
 static hipError_t launch_T(int op, const ChainArgs& a, hipStream_t st, hipEvent_t between, const PairPlan& pair) {
     const int T = a.T;  // T <= 32 is served by the one-wave kernels (launch_wave)
@@ -890,6 +912,7 @@ hipError_t launch_sequential_sum(int op, int dtype, const void* phi, const int32
     a.trans = trans;
     if (emit && T > 64) return hipErrorInvalidValue;  // the caller checks structured_supported(T) first
     if (wave_supported(T)) return launch_wave(op, dtype, a, st, between);
+    if (emit) return (T % 4) == 0 ? launch_structured_64<true>(op, a, st, between) : launch_structured_64<false>(op, a, st, between);
     // Pairs pay off when one workgroup per chain would leave at least half of the chip idle.
     static const int cus = [] {
         int dev = 0, n = 0;

@@ -86,7 +86,9 @@ __device__ __forceinline__ VitSpan vit_span(const VitArgs& a, int v) {
     return s;
 }
 
-template <typename G, typename TIN, bool ALIGNED>
+// STRUCT: potentials are trans + emit (float, T <= 64; a compile-time choice so that the dense path
+// keeps its loads free of branches).
+template <typename G, typename TIN, bool ALIGNED, bool STRUCT = false>
 __global__ __launch_bounds__(G::W) void viterbi_half_kernel(VitArgs a) {
     constexpr bool TURNED = vit_turns<G, ALIGNED>();
     __shared__ VitSmem<G, TURNED> sm;
@@ -106,12 +108,12 @@ __global__ __launch_bounds__(G::W) void viterbi_half_kernel(VitArgs a) {
 
     for (int k = tid; k < 2 * G::TCAP; k += G::W) (&sm.dvec[0][0])[k] = ninf;
     __syncthreads();
-    constexpr bool CAN_STRUCT = G::TCAP <= 64;
-    const bool structured = CAN_STRUCT && a.emit != nullptr;
+    constexpr bool CAN_STRUCT = STRUCT;
+    constexpr bool structured = STRUCT;
     const float* emb = structured ? a.emit + (size_t)b * N * T : nullptr;
     float tr[CAN_STRUCT ? ITEMS : 1][4];
     if constexpr (CAN_STRUCT) {
-        if (structured) load_tile<G, float, ALIGNED>(a.trans, T, c4, r0, tr);
+        load_tile<G, float, ALIGNED>(a.trans, T, c4, r0, tr);
     }
     if (tid < T) {
         if (dir == 0) {
@@ -129,13 +131,14 @@ __global__ __launch_bounds__(G::W) void viterbi_half_kernel(VitArgs a) {
     // forward: column maxima over rows, merged across waves through LDS
     auto fetch = [&](int i, float (&v)[ITEMS][4]) {
         if constexpr (CAN_STRUCT) {
-            if (structured) { load_emit4<ALIGNED>(emb + (size_t)i * T, T, c4, v[0]); return; }
+            load_emit4<ALIGNED>(emb + (size_t)i * T, T, c4, v[0]);
+            return;
         }
         load_tile<G, TIN, ALIGNED>(phib + (size_t)i * TT, T, c4, r0, v);
     };
     auto tile_ready = [&](float (&v)[ITEMS][4]) {
         if constexpr (CAN_STRUCT) {
-            if (structured) add_trans<ITEMS>(v, tr);
+            add_trans<ITEMS>(v, tr);
         }
     };
     auto fwd_step = [&](int i, float (&v)[ITEMS][4]) {
@@ -442,11 +445,29 @@ hipError_t launch_sequential_max(int dtype, const void* phi, const int32_t* leng
     return launch_any(dtype, VitArgs{phi, lengths, B, N, T, bp, mid, best_score, tags, 0, 1, nullptr, nullptr, nullptr}, st);
 }
 
+template <typename G, bool ALIGNED>
+static hipError_t launch_structured_geo(const VitArgs& a, hipStream_t st) {
+    hipLaunchKernelGGL((viterbi_half_kernel<G, float, ALIGNED, true>), dim3(2 * a.B), dim3(G::W), 0, st, a);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(viterbi_trace_kernel, dim3(a.B), dim3(128), 0, st, a);
+    return hipGetLastError();
+}
+template <bool ALIGNED>
+static hipError_t launch_structured_T(const VitArgs& a, hipStream_t st) {
+    if (a.T <= 4) return launch_structured_geo<Geo<1, 1, 1>, ALIGNED>(a, st);
+    if (a.T <= 8) return launch_structured_geo<Geo<2, 1, 1>, ALIGNED>(a, st);
+    if (a.T <= 16) return launch_structured_geo<Geo<4, 1, 1>, ALIGNED>(a, st);
+    if (a.T <= 32) return launch_structured_geo<Geo<8, 4, 1>, ALIGNED>(a, st);
+    return launch_structured_geo<Geo<16, 4, 4>, ALIGNED>(a, st);
+}
+
 // The same from structured potentials (float emit [B][N][T] + trans [T][T]; T <= 64).
 hipError_t launch_structured_max(const float* emit, const float* trans, const int32_t* lengths, int B, int N, int T,
                                  uint8_t* bp, double* mid, float* best_score, int32_t* tags, hipStream_t st) {
     if (T > 64) return hipErrorInvalidValue;
-    return launch_any(0, VitArgs{nullptr, lengths, B, N, T, bp, mid, best_score, tags, 0, 1, nullptr, emit, trans}, st);
+    const VitArgs a{nullptr, lengths, B, N, T, bp, mid, best_score, tags, 0, 1, nullptr, emit, trans};
+    return (T % 4) == 0 ? launch_structured_T<true>(a, st) : launch_structured_T<false>(a, st);
 }
 
 // Best path inside every chunk between the tags the max-plus scan has pinned at the chunk ends.

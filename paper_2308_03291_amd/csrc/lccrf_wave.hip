@@ -22,6 +22,8 @@
 #include "lccrf_device.h"
 #include "lccrf_launch.h"
 
+#include <type_traits>
+
 namespace lccrf {
 
 template <int TP>
@@ -255,7 +257,9 @@ constexpr int wave_ring_depth(int TP, bool second_pass) { return second_pass ? (
 
 // ---------------------------------------------------------------------------------------
 // Pass 1: both half chains, vectors stored.
-template <int TP, typename TIN, bool ALIGNED, bool WITH_H>
+// STRUCT: potentials are trans + emit (a compile-time choice: a branch around the loads would cost the
+// exact wait counts that keep the ring of tiles in flight).
+template <int TP, typename TIN, bool ALIGNED, bool WITH_H, bool STRUCT>
 __global__ __launch_bounds__(64) void wave_half_kernel(ChainArgs a) {
     using W = WGeo<TP>;
     constexpr int R = W::R, PF = wave_ring_depth(TP, false);
@@ -270,12 +274,12 @@ __global__ __launch_bounds__(64) void wave_half_kernel(ChainArgs a) {
     const TIN* phib = static_cast<const TIN*>(a.phi) + (size_t)b * N * TT;
     const bool exact_only = a.exact_only != 0;
     float ring[PF][R][4];
-    const bool structured = a.emit != nullptr;
+    constexpr bool structured = STRUCT;
     const float* emb = structured ? a.emit + (size_t)b * N * T : nullptr;
     float tr[R][4];
-    if (structured) wave_load<TP, float, ALIGNED>(a.trans, T, lane, tr);
+    if constexpr (structured) wave_load<TP, float, ALIGNED>(a.trans, T, lane, tr);
     auto load = [&](int i, int slot) {
-        if (structured) wave_load_emit<TP, ALIGNED>(emb + (size_t)i * T, T, lane, ring[slot]);
+        if constexpr (structured) wave_load_emit<TP, ALIGNED>(emb + (size_t)i * T, T, lane, ring[slot]);
         else wave_load<TP, TIN, ALIGNED>(phib + (size_t)i * TT, T, lane, ring[slot]);
     };
     const float none4[4] = {0.f, 0.f, 0.f, 0.f};
@@ -312,7 +316,7 @@ __global__ __launch_bounds__(64) void wave_half_kernel(ChainArgs a) {
         };
         float hc[4] = {0.f, 0.f, 0.f, 0.f};  // entropy of the path behind each tag, column form
         walk<PF>(p0 + 1, h, +1, load, [&](int i, int slot) {
-            if (structured) add_trans<R>(ring[slot], tr);
+            if constexpr (structured) add_trans<R>(ring[slot], tr);
             const float d = settle(i - 1);
             float ua[R], hrow[R];
             col_to_row<TP>(vc, ua, lane);
@@ -355,7 +359,7 @@ __global__ __launch_bounds__(64) void wave_half_kernel(ChainArgs a) {
 #pragma unroll
         for (int k = 0; k < R; ++k) hr[k] = 0.f;
         walk<PF>(e, h + 1, -1, load, [&](int i, int slot) {
-            if (structured) add_trans<R>(ring[slot], tr);
+            if constexpr (structured) add_trans<R>(ring[slot], tr);
             const float d = settle(i);
             float ub[4], hcol[4];
             row_to_col<TP>(vr, ub, lane);
@@ -373,7 +377,7 @@ __global__ __launch_bounds__(64) void wave_half_kernel(ChainArgs a) {
 
 // ---------------------------------------------------------------------------------------
 // Pass 2: both chains continue past the meeting point and write the marginals.
-template <int TP, typename TIN, bool ALIGNED>
+template <int TP, typename TIN, bool ALIGNED, bool STRUCT>
 __global__ __launch_bounds__(64) void wave_marginal_kernel(ChainArgs a) {
     using W = WGeo<TP>;
     constexpr int R = W::R, PF = wave_ring_depth(TP, true);
@@ -424,12 +428,12 @@ __global__ __launch_bounds__(64) void wave_marginal_kernel(ChainArgs a) {
     if (dir == 0 && sp.c == 0 && lane == 0 && a.logZ) a.logZ[b] = (float)(lz2 * kLn2);
 
     float ring[PF][R][4];
-    const bool structured = a.emit != nullptr;
+    constexpr bool structured = STRUCT;
     const float* emb = structured ? a.emit + (size_t)b * N * T : nullptr;
     float tr[R][4];
-    if (structured) wave_load<TP, float, ALIGNED>(a.trans, T, lane, tr);
+    if constexpr (structured) wave_load<TP, float, ALIGNED>(a.trans, T, lane, tr);
     auto load_phi = [&](int i, int slot) {
-        if (structured) wave_load_emit<TP, ALIGNED>(emb + (size_t)i * T, T, lane, ring[slot]);
+        if constexpr (structured) wave_load_emit<TP, ALIGNED>(emb + (size_t)i * T, T, lane, ring[slot]);
         else wave_load<TP, TIN, ALIGNED>(phib + (size_t)i * TT, T, lane, ring[slot]);
     };
     float kappa = 0.f, tot = 0.f;
@@ -451,7 +455,7 @@ __global__ __launch_bounds__(64) void wave_marginal_kernel(ChainArgs a) {
             ob[slot] = a.Ob[vb + i];
         };
         walk<PF>(h + 1, e, +1, load, [&](int i, int slot) {
-            if (structured) add_trans<R>(ring[slot], tr);
+            if constexpr (structured) add_trans<R>(ring[slot], tr);
             const float d = finite_or_zero(xor_max<1, W::CG>(max4(vc)));
             kappa += drift_of(tot);
             O += (double)d;
@@ -479,7 +483,7 @@ __global__ __launch_bounds__(64) void wave_marginal_kernel(ChainArgs a) {
             oa[slot] = a.Oa[vb + i - 1];
         };
         walk<PF>(h, p0 + 1, -1, load, [&](int i, int slot) {
-            if (structured) add_trans<R>(ring[slot], tr);
+            if constexpr (structured) add_trans<R>(ring[slot], tr);
             float m = vr[0];
 #pragma unroll
             for (int k = 1; k < R; ++k) m = fmaxf(m, vr[k]);
@@ -525,12 +529,21 @@ bool wave_supported(int T) { return T >= 1 && T <= 32; }
 template <int TP, typename TIN, bool ALIGNED>
 static hipError_t launch_wave_tp(bool second_pass, const ChainArgs& a, hipStream_t st) {
     const dim3 grid(2 * a.B * a.C);
+    if constexpr (std::is_same<TIN, float>::value) {
+        if (a.emit) {  // structured potentials: float only, no entropy mode
+            if (second_pass)
+                hipLaunchKernelGGL((wave_marginal_kernel<TP, float, ALIGNED, true>), grid, dim3(64), 0, st, a);
+            else
+                hipLaunchKernelGGL((wave_half_kernel<TP, float, ALIGNED, false, true>), grid, dim3(64), 0, st, a);
+            return hipGetLastError();
+        }
+    }
     if (second_pass)
-        hipLaunchKernelGGL((wave_marginal_kernel<TP, TIN, ALIGNED>), grid, dim3(64), 0, st, a);
+        hipLaunchKernelGGL((wave_marginal_kernel<TP, TIN, ALIGNED, false>), grid, dim3(64), 0, st, a);
     else if (a.ha)
-        hipLaunchKernelGGL((wave_half_kernel<TP, TIN, ALIGNED, true>), grid, dim3(64), 0, st, a);
+        hipLaunchKernelGGL((wave_half_kernel<TP, TIN, ALIGNED, true, false>), grid, dim3(64), 0, st, a);
     else
-        hipLaunchKernelGGL((wave_half_kernel<TP, TIN, ALIGNED, false>), grid, dim3(64), 0, st, a);
+        hipLaunchKernelGGL((wave_half_kernel<TP, TIN, ALIGNED, false, false>), grid, dim3(64), 0, st, a);
     return hipGetLastError();
 }
 
