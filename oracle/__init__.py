@@ -41,6 +41,8 @@ def _load():
     lib.lccrf_oracle_log_prob.restype = i
     lib.lccrf_oracle_cross_entropy.argtypes = [vp, vp, i, ip, i, i, i, dp]
     lib.lccrf_oracle_cross_entropy.restype = i
+    lib.lccrf_oracle_sample.argtypes = [vp, i, ip, vp, i, i, i, vp, dp]
+    lib.lccrf_oracle_sample.restype = i
     lib.lccrf_oracle_threads.argtypes = []
     lib.lccrf_oracle_threads.restype = i
     _lib = lib
@@ -186,3 +188,21 @@ def cross_entropy(phi_p, phi_q, lengths=None) -> np.ndarray:
 
 def entropy(phi, lengths=None) -> np.ndarray:
     return cross_entropy(phi, phi, lengths)
+
+
+def sample(phi, uniforms, lengths=None):
+    """Forward-filtering backward-sampling with the given uniforms [B, N] (float32 in [0, 1)):
+    (tags [B, N] int32 with -1 past the length, margin [B] float64: how far, relative to the total
+    weight, the closest draw of the chain was from picking a neighbouring tag)."""
+    lib = _load()
+    arr, dt, (B, N, T, T2) = _as_storage(phi)
+    assert T == T2
+    l = _lengths(lengths, B)
+    u = np.ascontiguousarray(np.asarray(uniforms), dtype=np.float32)
+    assert u.shape == (B, N)
+    tags = np.empty((B, N), dtype=np.int32)
+    margin = np.empty((B,))
+    rc = lib.lccrf_oracle_sample(_ptr(arr), dt, _ptr(l), _ptr(u), B, N, T, _ptr(tags), _ptr(margin))
+    if rc != 0:
+        raise RuntimeError(f"oracle error {rc}")
+    return tags, margin

@@ -257,6 +257,70 @@ int lccrf_oracle_cross_entropy(const void *phi_p, const void *phi_q, int dtype, 
 }
 
 /*
+ * Forward-filtering backward-sampling (section "Sampling a Structure"): with alpha from the
+ * forward algorithm, y_{L-1} is drawn from p(t) ~ exp(alpha_{L-1}(t)) and then, going down,
+ * y_{i-1} from p(s | y_i) ~ exp(alpha_{i-1}(s) + phi[i][s][y_i]).  The randomness is an input:
+ * uniforms[b][i] in [0, 1) decides position i by inversion of the cumulative distribution over
+ * tags in ascending order: the chosen tag is the smallest t whose cumulative weight exceeds
+ * u * (total weight); if rounding leaves none, the last tag of positive weight.
+ *
+ * margin[b] (optional): the smallest distance, over the positions of the chain, between
+ * u * total and the nearest boundary of the chosen tag's interval, relative to the total: how
+ * far the draw was from choosing a neighbouring tag.  A sequence without a finite path gets
+ * tags 0 and margin 0.  tags[b][i] = -1 for i >= L.
+ */
+int lccrf_oracle_sample(const void *phi, int dtype, const int32_t *lengths, const float *uniforms,
+                        int B, int N, int T, int32_t *tags, double *margin /* may be NULL */)
+{
+    if (!phi || !uniforms || !tags || B < 1 || N < 1 || T < 1 || (dtype != 0 && dtype != 1)) return -1;
+    int err = 0;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int b = 0; b < B; ++b) {
+        int L = clamp_len(lengths, b, N);
+        size_t base = (size_t)b * N * T * T;
+        int32_t *y = tags + (size_t)b * N;
+        for (int i = 0; i < N; ++i) y[i] = i < L ? 0 : -1;
+        if (margin) margin[b] = L == 0 ? 1.0 : 0.0;
+        if (L == 0) continue;
+        double *alpha = (double *)malloc(sizeof(double) * (size_t)L * T);
+        double *tmp = (double *)malloc(sizeof(double) * (size_t)T);
+        double *w = (double *)malloc(sizeof(double) * (size_t)T);
+        if (!alpha || !tmp || !w) { err = 1; free(alpha); free(tmp); free(w); continue; }
+        forward_one(phi, dtype, base, L, T, alpha, tmp);
+        if (logsumexp(alpha + (size_t)(L - 1) * T, T) == -INFINITY) { free(alpha); free(tmp); free(w); continue; }
+        double worst = 1.0;
+        for (int i = L - 1; i >= 0; --i) {
+            /* log-weights of the tags of position i */
+            for (int s = 0; s < T; ++s) {
+                w[s] = alpha[(size_t)i * T + s];
+                if (i < L - 1)
+                    w[s] += phi_at(phi, dtype, base + (size_t)(i + 1) * T * T + (size_t)s * T + (size_t)y[i + 1]);
+            }
+            double m = -INFINITY, total = 0.0;
+            for (int s = 0; s < T; ++s) if (w[s] > m) m = w[s];
+            for (int s = 0; s < T; ++s) { w[s] = exp(w[s] - m); total += w[s]; }
+            double target = (double)uniforms[(size_t)b * N + i] * total, cum = 0.0;
+            int pick = -1, last_pos = 0;
+            double lo = 0.0, hi = 0.0;
+            for (int s = 0; s < T; ++s) {
+                if (w[s] > 0.0) last_pos = s;
+                if (pick < 0 && cum + w[s] > target) { pick = s; lo = cum; hi = cum + w[s]; }
+                cum += w[s];
+            }
+            if (pick < 0) { pick = last_pos; lo = hi = target; }
+            y[i] = pick;
+            double d1 = (target - lo) / total, d2 = (hi - target) / total;
+            if (pick == 0 || lo == 0.0) d1 = 1.0;           /* nothing below to fall into */
+            if (d1 < worst) worst = d1;
+            if (d2 < worst) worst = d2;
+        }
+        if (margin) margin[b] = worst;
+        free(alpha); free(tmp); free(w);
+    }
+    return err ? -2 : 0;
+}
+
+/*
  * Max-plus semiring.  delta[i][t] = best score of a prefix ending in t;
  * bp[i][t] = smallest s attaining it.  The last tag is the smallest t attaining
  * max_t delta[L-1][t]; earlier tags follow the back-pointers.  tags[b][i] = -1 for

@@ -442,3 +442,52 @@ def test_entropy_with_forbidden_edges(oracle_mod):
     dead = phi.copy()
     dead[0, 3] = -np.inf
     assert np.isnan(oracle_mod.entropy(dead)[0])
+
+
+# ---------------------------------------------------------------------------------------
+# forward-filtering backward-sampling (section "Sampling a Structure")
+
+def test_sampling_follows_the_distribution(oracle_mod):
+    """With many independent uniforms the empirical frequency of every path of a small chain matches
+    its enumerated probability (a chi-square-sized bound), which pins the conditional used at each
+    step: a wrong index or a transposed matrix would change the frequencies."""
+    T, N, L = 3, 4, 4
+    phi = _rand(71, 1, N, T, scale=1.2)
+    paths = brute.all_paths(T, L)
+    sc = brute.path_scores(phi[0].astype(np.float64), L, paths)
+    p = np.exp(sc - scipy.special.logsumexp(sc))
+    M = 200000
+    rng = np.random.default_rng(72)
+    u = rng.random((M, N), dtype=np.float32)
+    tags, _ = oracle_mod.sample(np.repeat(phi, M, axis=0), u)
+    codes = (tags * (T ** np.arange(N - 1, -1, -1))).sum(1)
+    want_codes = (paths * (T ** np.arange(N - 1, -1, -1))).sum(1)
+    freq = np.array([(codes == c).mean() for c in want_codes])
+    assert np.abs(freq - p).max() < 5 * np.sqrt(p.max() / M)
+
+
+def test_sampling_inversion_rule(oracle_mod):
+    """One position, known weights: the tag is the first whose cumulative probability exceeds u."""
+    T = 4
+    phi = np.zeros((5, 1, T, T), dtype=np.float32)
+    phi[:, 0, 0, :] = np.log(np.array([0.1, 0.2, 0.3, 0.4], dtype=np.float32))
+    u = np.array([[0.05], [0.1001], [0.29], [0.61], [0.9999]], dtype=np.float32)
+    tags, margin = oracle_mod.sample(phi, u)
+    assert tags[:, 0].tolist() == [0, 1, 1, 3, 3]
+    assert margin[0] == pytest.approx(0.05, abs=1e-6) and margin[2] == pytest.approx(0.01, abs=1e-6)
+
+
+def test_sampling_special_cases(oracle_mod):
+    phi = _rand(73, 3, 6, 3)
+    phi[1, 3, :, 1] = -np.inf          # tag 1 is impossible at position 3
+    lens = np.array([6, 6, 2], dtype=np.int32)
+    u = np.random.default_rng(74).random((3, 6), dtype=np.float32)
+    tags, _ = oracle_mod.sample(phi, u, lens)
+    assert tags[1, 3] != 1 and (tags[2, 2:] == -1).all() and ((tags[2, :2] >= 0) & (tags[2, :2] < 3)).all()
+    # a sampled path has positive probability
+    assert np.isfinite(oracle_mod.log_prob(phi, tags, lens)).all()
+    # peaked potentials: the sample is the best path whatever the uniforms are (away from 0 and 1)
+    peaked = (_rand(75, 2, 7, 4) * 40).astype(np.float32)
+    _, best, _ = oracle_mod.viterbi(peaked)
+    tags, _ = oracle_mod.sample(peaked, np.full((2, 7), 0.5, dtype=np.float32))
+    assert np.array_equal(tags, best)
