@@ -55,7 +55,8 @@ typedef enum {
     LCCRF_OP_MARGINALS = 1,
     LCCRF_OP_ARGMAX = 2,
     LCCRF_OP_LOG_PROB = 3,
-    LCCRF_OP_ENTROPY = 4
+    LCCRF_OP_ENTROPY = 4,
+    LCCRF_OP_SAMPLE = 5
 } lccrf_op;
 
 /* How the recursion over positions is scheduled.  Results are the same up to
@@ -176,6 +177,21 @@ int lccrf_log_prob(const void* phi, lccrf_dtype dt, const int32_t* lengths, cons
  */
 int lccrf_entropy(const void* phi, lccrf_dtype dt, const int32_t* lengths, int B, int N, int T,
                   float* entropy, void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * One sample per sequence by forward-filtering backward-sampling (paper, section "Sampling a
+ * Structure"): the forward algorithm, then y_{L-1} ~ exp(alpha_{L-1}(t)) and, going down,
+ * y_i ~ exp(alpha_i(s) + phi[i+1][s][y_{i+1}]).  The randomness is the caller's: uniforms[b][i]
+ * in [0, 1) decides position i by inversion of the cumulative weights over ascending tags (the
+ * smallest tag whose cumulative weight exceeds u * total), so a call is reproducible and
+ * samples are independent exactly as far as the uniforms are.
+ *   uniforms  [B][N] float32 (device); entries past the lengths are ignored.
+ *   tags      [B][N] int32 (device), -1 past the length; all 0 for a chain without a finite path.
+ * Workspace: lccrf_workspace_bytes(LCCRF_OP_SAMPLE, ...).  Errors as lccrf_log_partition.
+ */
+int lccrf_sample(const void* phi, lccrf_dtype dt, const int32_t* lengths, const float* uniforms,
+                 int B, int N, int T, int32_t* tags,
+                 void* workspace, size_t workspace_bytes, void* stream);
 
 /*
  * The three queries from STRUCTURED potentials: phi[b][i][s][t] = trans[s][t] + emit[b][i][t], the

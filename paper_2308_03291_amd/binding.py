@@ -23,14 +23,14 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "liblccrf.so")
 
 LCCRF_F32, LCCRF_BF16 = 0, 1
-OP_LOGZ, OP_MARGINALS, OP_ARGMAX, OP_LOG_PROB, OP_ENTROPY = 0, 1, 2, 3, 4
+OP_LOGZ, OP_MARGINALS, OP_ARGMAX, OP_LOG_PROB, OP_ENTROPY, OP_SAMPLE = 0, 1, 2, 3, 4, 5
 ALGO_AUTO, ALGO_SEQUENTIAL, ALGO_SCAN, ALGO_SEQUENTIAL_EXACT = 0, 1, 2, 3
 MAX_T = 256
 
 EXPORTS = (
     "lccrf_workspace_bytes", "lccrf_log_partition", "lccrf_marginals", "lccrf_argmax",
     "lccrf_log_partition_algo", "lccrf_marginals_algo", "lccrf_argmax_algo",
-    "lccrf_marginals_timed", "lccrf_log_prob", "lccrf_entropy", "lccrf_log_partition_structured",
+    "lccrf_marginals_timed", "lccrf_log_prob", "lccrf_entropy", "lccrf_sample", "lccrf_log_partition_structured",
     "lccrf_marginals_structured", "lccrf_argmax_structured", "lccrf_set_scan_chunk", "lccrf_strerror",
     "lccrf_version",
 )
@@ -73,6 +73,8 @@ def load_library() -> ctypes.CDLL:
     lib.lccrf_log_prob.restype = i
     lib.lccrf_entropy.argtypes = base + [vp, vp, sz, vp]
     lib.lccrf_entropy.restype = i
+    lib.lccrf_sample.argtypes = [vp, i, vp, vp, i, i, i, vp, vp, sz, vp]
+    lib.lccrf_sample.restype = i
     sbase = [vp, vp, vp, i, i, i]
     lib.lccrf_log_partition_structured.argtypes = sbase + [vp, vp, sz, vp]
     lib.lccrf_marginals_structured.argtypes = sbase + [vp, vp, vp, sz, vp]
@@ -227,6 +229,25 @@ def lccrf_entropy(phi: torch.Tensor, lengths: Optional[torch.Tensor] = None, *,
         rc = lib.lccrf_entropy(phi.data_ptr(), dt, _len_ptr(lengths, B, phi.device), B, N, T,
                                out.data_ptr(), ws.data_ptr(), nws, _stream(phi.device))
     _check(rc, "lccrf_entropy")
+    return out
+
+
+def lccrf_sample(phi: torch.Tensor, uniforms: torch.Tensor, lengths: Optional[torch.Tensor] = None, *,
+                 out: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """One sampled tag path per sequence [B, N] int32 (-1 past the length), drawn by forward-filtering
+    backward-sampling from the given uniforms (float32 [B, N] in [0, 1) on phi's device)."""
+    lib = load_library()
+    dt, B, N, T = _phi_args(phi)
+    if uniforms.dtype != torch.float32 or tuple(uniforms.shape) != (B, N) or not uniforms.is_contiguous() \
+            or uniforms.device != phi.device:
+        raise LccrfError("uniforms must be a contiguous float32 [B, N] tensor on phi's device")
+    ws, nws = _workspace(OP_SAMPLE, B, N, T, dt, phi.device, workspace)
+    if out is None:
+        out = torch.empty(B, N, dtype=torch.int32, device=phi.device)
+    with torch.cuda.device(phi.device):
+        rc = lib.lccrf_sample(phi.data_ptr(), dt, _len_ptr(lengths, B, phi.device), uniforms.data_ptr(), B, N, T,
+                              out.data_ptr(), ws.data_ptr(), nws, _stream(phi.device))
+    _check(rc, "lccrf_sample")
     return out
 
 

@@ -140,7 +140,8 @@ size_t lccrf_workspace_bytes(lccrf_op op, int B, int N, int T, lccrf_dtype dt) {
         case LCCRF_OP_LOGZ:
         case LCCRF_OP_MARGINALS:
         case LCCRF_OP_LOG_PROB:
-        case LCCRF_OP_ENTROPY: return sum_workspace(B, N, T).total;
+        case LCCRF_OP_ENTROPY:
+        case LCCRF_OP_SAMPLE: return sum_workspace(B, N, T).total;
         case LCCRF_OP_ARGMAX: return max_workspace(B, N, T).total;
         default: return 0;
     }
@@ -253,6 +254,24 @@ int lccrf_entropy(const void* phi, lccrf_dtype dt, const int32_t* lengths, int B
     return e == hipSuccess ? LCCRF_OK : LCCRF_ELAUNCH;
 }
 
+int lccrf_sample(const void* phi, lccrf_dtype dt, const int32_t* lengths, const float* uniforms, int B, int N, int T,
+                 int32_t* tags, void* workspace, size_t workspace_bytes, void* stream) {
+    const size_t need = lccrf_workspace_bytes(LCCRF_OP_SAMPLE, B, N, T, dt);
+    const int rc = check_common(phi, dt, B, N, T, workspace, workspace_bytes, need, LCCRF_ALGO_AUTO);
+    if (rc != LCCRF_OK) return rc;
+    if (!uniforms || !tags) return LCCRF_ENULL;
+    if (!aligned_to(uniforms, 4) || !aligned_to(tags, 4) || (lengths && !aligned_to(lengths, 4))) return LCCRF_EALIGN;
+    const SumWorkspace w = sum_workspace(B, N, T);
+    char* base = static_cast<char*>(workspace);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    float* ua = reinterpret_cast<float*>(base + w.ua);
+    hipError_t e = lccrf::launch_full_forward(dt, phi, lengths, B, N, T, ua, reinterpret_cast<float*>(base + w.ub),
+                                              reinterpret_cast<double*>(base + w.Oa),
+                                              reinterpret_cast<double*>(base + w.Ob), st);
+    if (e == hipSuccess) e = lccrf::launch_backward_sample(dt, phi, lengths, ua, uniforms, B, N, T, tags, st);
+    return e == hipSuccess ? LCCRF_OK : LCCRF_ELAUNCH;
+}
+
 // Common checks of the structured calls.
 static int check_structured(const float* emit, const float* trans, const int32_t* lengths, int B, int N, int T,
                             const void* ws, size_t ws_bytes, size_t need) {
@@ -329,6 +348,6 @@ int lccrf_set_scan_chunk(int chunk) {
     return LCCRF_OK;
 }
 
-int lccrf_version(void) { return 103; }
+int lccrf_version(void) { return 104; }
 
 }  // extern "C"

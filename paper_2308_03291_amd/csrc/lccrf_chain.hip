@@ -389,7 +389,7 @@ __device__ __forceinline__ void forward_half_turned(ChainSmem<G>& sm, float* __r
     static_assert(G::LPR == 32 && G::WAVES == 16 && G::ITEMS == 4 && PF == 4, "laid out for 1024 threads, T <= 128");
     const int lane = tid & 63, wave = tid >> 6;
     const int b = sp.b, N = a.N, T = a.T;
-    const int p0 = sp.p0, h = meeting_point(sp.p0, sp.e);
+    const int p0 = sp.p0, h = forward_end(a, sp.p0, sp.e);
     const int c4 = 4 * (tid % 32), r0 = tid / 32;
     const size_t TT = (size_t)T * T, vb = (size_t)b * N;
     const TIN* phib = static_cast<const TIN*>(a.phi) + (size_t)b * N * TT;
@@ -527,7 +527,8 @@ __global__ __launch_bounds__(G::W) void chain_half_kernel(ChainArgs a) {
     }
     if (sp.empty) return;
     const int p0 = sp.p0, e = sp.e;
-    const int h = meeting_point(p0, e);
+    const int h = forward_end(a, p0, e);
+    if (a.full_forward && dir == 1) return;
     const int c4 = 4 * (tid % G::LPR), r0 = tid / G::LPR;
     const TIN* phib = static_cast<const TIN*>(a.phi) + (size_t)b * N * T * T;
     const size_t TT = (size_t)T * T;
@@ -841,6 +842,7 @@ static hipError_t launch_geo(int op, ChainArgs a, hipStream_t st, hipEvent_t bet
         e = hipEventRecord(between, st);
         if (e != hipSuccess) return e;
     }
+    if (op == 2) return hipSuccess;  // first pass only
     if (op == 0) {
         hipLaunchKernelGGL(logz_combine_kernel, dim3(a.B), dim3(64), 0, st, a);
         return hipGetLastError();
@@ -892,6 +894,7 @@ static hipError_t launch_wave(int op, int dtype, const ChainArgs& a, hipStream_t
         e = hipEventRecord(between, st);
         if (e != hipSuccess) return e;
     }
+    if (op == 2) return hipSuccess;  // first pass only
     if (op == 0) {
         hipLaunchKernelGGL(logz_combine_kernel, dim3(a.B), dim3(64), 0, st, a);
         return hipGetLastError();
@@ -900,6 +903,19 @@ static hipError_t launch_wave(int op, int dtype, const ChainArgs& a, hipStream_t
 }
 
 bool structured_supported(int T) { return T >= 1 && T <= 64; }
+
+// Forward chains over whole sequences, every alpha stored (ua, Oa): the first pass of sampling.
+hipError_t launch_full_forward(int dtype, const void* phi, const int32_t* lengths, int B, int N, int T, float* ua,
+                               float* ub, double* Oa, double* Ob, hipStream_t st) {
+    ChainArgs a{phi, lengths, B, N, T, ua, ub, Oa, Ob, nullptr, nullptr, 0, nullptr, 0, 1, nullptr, nullptr, nullptr, nullptr};
+    a.full_forward = 1;
+    if (wave_supported(T)) return launch_wave(2, dtype, a, st, nullptr);
+    const PairPlan pair{nullptr, nullptr, dtype};
+    const bool aligned = (T % 4) == 0;
+    if (dtype == 0)
+        return aligned ? launch_T<float, true>(2, a, st, nullptr, pair) : launch_T<float, false>(2, a, st, nullptr, pair);
+    return aligned ? launch_T<uint16_t, true>(2, a, st, nullptr, pair) : launch_T<uint16_t, false>(2, a, st, nullptr, pair);
+}
 
 // op: 0 = logZ only, 1 = marginals (+ logZ).  Workspace pointers already carved by the caller.
 hipError_t launch_sequential_sum(int op, int dtype, const void* phi, const int32_t* lengths, int B, int N, int T,

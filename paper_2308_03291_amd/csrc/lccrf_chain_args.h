@@ -40,6 +40,9 @@ struct ChainArgs {
     // phi[b][i][s][t] = trans[s][t] + emit[b][i][t].
     const float* emit;   // [B][N][T]
     const float* trans;  // [T][T]
+    // 1: the forward chain runs over the whole span and stores every alpha; no backward chain
+    // (first pass of sampling, whose backward sweep needs alpha everywhere).
+    int full_forward;
 };
 
 // The stretch of positions one pair of workgroups handles: all of a sequence, or one chunk.
@@ -76,6 +79,8 @@ __device__ __forceinline__ Span make_span(const ChainArgs& a, int v) {
 // p0 .. h, the backward chain h .. e.  Every kernel of both passes derives it from here.
 // (The middle: uneven splits were measured and lose more in the second pass than they gain in the first.)
 __host__ __device__ __forceinline__ int meeting_point(int p0, int e) { return p0 + (e - p0 + 1) / 2; }
+// Last position of the forward chain in a first pass: the meeting point, or the end of the span.
+__device__ __forceinline__ int forward_end(const ChainArgs& a, int p0, int e) { return a.full_forward ? e : meeting_point(p0, e); }
 
 // One-wave-per-chain kernels for T <= 32 (lccrf_wave.hip): one pass over all chains of `a`
 // (a.C = 1 for whole sequences).  The first pass stores the vectors of both half chains, the

@@ -301,4 +301,108 @@ hipError_t launch_entropy(int dtype, const void* phi, const int32_t* lengths, in
     return launch_entropy_combine(a, H, st);
 }
 
+// ---------------------------------------------------------------------------------------
+// Backward sweep of forward-filtering backward-sampling (paper, section "Sampling a Structure"):
+// y_{L-1} ~ exp(alpha_{L-1}(t)), then y_i ~ exp(alpha_i(s) + phi_{i+1}(s, y_{i+1})) going down.
+// The randomness is an input: uniforms[b][i] decides position i by inversion of the cumulative
+// weights over ascending tags (the smallest tag whose cumulative weight exceeds u * total; the
+// last tag of positive weight if rounding leaves none).  One wave per sequence; lane l owns the
+// K consecutive tags l K .. l K + K - 1 so that the lane-wise prefix sums keep the tag order.
+template <typename TIN, int K>
+__global__ __launch_bounds__(64) void backward_sample_kernel(const TIN* __restrict__ phi, const int32_t* __restrict__ lengths,
+                                                            const float* __restrict__ ua, const float* __restrict__ uniforms,
+                                                            int N, int T, int32_t* __restrict__ tags) {
+    const int b = blockIdx.x, lane = threadIdx.x;
+    const int L = clamp_length(lengths, b, N);
+    int32_t* y = tags + (size_t)b * N;
+    for (int i = L + lane; i < N; i += 64) y[i] = -1;
+    if (L == 0) return;
+    const size_t TT = (size_t)T * T;
+    const TIN* phib = phi + (size_t)b * N * TT;
+    const float* uab = ua + (size_t)b * N * T;
+    const float* ub = uniforms + (size_t)b * N;
+    int next = 0;
+    bool dead = false;
+    float a_cur[K];
+#pragma unroll
+    for (int k = 0; k < K; ++k) {
+        const int s = lane * K + k;
+        a_cur[k] = s < T ? uab[(size_t)(L - 1) * T + s] : LCCRF_NEG_INF;
+    }
+    for (int i = L - 1; i >= 0; --i) {
+        float a_prev[K];  // alpha of the position below, requested before this position's dependent work
+#pragma unroll
+        for (int k = 0; k < K; ++k) {
+            const int s = lane * K + k;
+            a_prev[k] = (i > 0 && s < T) ? uab[(size_t)(i - 1) * T + s] : LCCRF_NEG_INF;
+        }
+        float w[K], m = LCCRF_NEG_INF;
+#pragma unroll
+        for (int k = 0; k < K; ++k) {
+            const int s = lane * K + k;
+            w[k] = a_cur[k];
+            if (i < L - 1 && s < T) w[k] += Elem<TIN>::get(phib + (size_t)(i + 1) * TT + (size_t)s * T + next) * kLog2e;
+            m = fmaxf(m, w[k]);
+        }
+        m = xor_max<1, 64>(m);
+        int pick = 0;
+        if (m == LCCRF_NEG_INF) {
+            dead = true;  // no finite path: all tags 0
+        } else {
+            float part = 0.f;
+#pragma unroll
+            for (int k = 0; k < K; ++k) {
+                w[k] = ex2(w[k] - m);
+                part += w[k];
+            }
+            // inclusive prefix sum over lanes (ascending lane = ascending tag)
+            float incl = part;
+#pragma unroll
+            for (int off = 1; off < 64; off <<= 1) {
+                const float v = __shfl_up(incl, off, 64);
+                if (lane >= off) incl += v;
+            }
+            const float total = __shfl(incl, 63, 64);
+            const float target = ub[i] * total;
+            float cum = incl - part;
+            int first_over = 0x7fffffff, last_pos = -1;
+#pragma unroll
+            for (int k = 0; k < K; ++k) {
+                const int s = lane * K + k;
+                cum += w[k];
+                if (w[k] > 0.f) last_pos = s;
+                if (first_over == 0x7fffffff && cum > target && s < T) first_over = s;
+            }
+#pragma unroll
+            for (int off = 1; off < 64; off <<= 1) {
+                first_over = min(first_over, __shfl_xor(first_over, off, 64));
+                last_pos = max(last_pos, __shfl_xor(last_pos, off, 64));
+            }
+            pick = first_over != 0x7fffffff ? first_over : last_pos;
+        }
+        if (dead) break;
+        if (lane == 0) y[i] = pick;
+        next = pick;
+#pragma unroll
+        for (int k = 0; k < K; ++k) a_cur[k] = a_prev[k];
+    }
+    if (dead)
+        for (int i = lane; i < L; i += 64) y[i] = 0;
+}
+
+template <typename TIN>
+static hipError_t launch_sample_T(const TIN* phi, const int32_t* lengths, const float* ua, const float* uniforms, int B, int N,
+                                  int T, int32_t* tags, hipStream_t st) {
+    if (T <= 64) hipLaunchKernelGGL((backward_sample_kernel<TIN, 1>), dim3(B), dim3(64), 0, st, phi, lengths, ua, uniforms, N, T, tags);
+    else if (T <= 128) hipLaunchKernelGGL((backward_sample_kernel<TIN, 2>), dim3(B), dim3(64), 0, st, phi, lengths, ua, uniforms, N, T, tags);
+    else hipLaunchKernelGGL((backward_sample_kernel<TIN, 4>), dim3(B), dim3(64), 0, st, phi, lengths, ua, uniforms, N, T, tags);
+    return hipGetLastError();
+}
+
+hipError_t launch_backward_sample(int dtype, const void* phi, const int32_t* lengths, const float* ua,
+                                  const float* uniforms, int B, int N, int T, int32_t* tags, hipStream_t st) {
+    if (dtype == 0) return launch_sample_T(static_cast<const float*>(phi), lengths, ua, uniforms, B, N, T, tags, st);
+    return launch_sample_T(static_cast<const uint16_t*>(phi), lengths, ua, uniforms, B, N, T, tags, st);
+}
+
 }  // namespace lccrf

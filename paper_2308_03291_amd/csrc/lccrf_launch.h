@@ -19,6 +19,12 @@ hipError_t launch_sequential_sum(int op, int dtype, const void* phi, const int32
                                  hipStream_t st, hipEvent_t between = nullptr, bool exact_only = false,
                                  unsigned long long* mail = nullptr, int* failed = nullptr, double* logZ64 = nullptr,
                                  const float* emit = nullptr, const float* trans = nullptr);
+// Sampling (lccrf_chain.hip, lccrf_extras.hip): forward chains over whole sequences with every alpha
+// stored, then the backward sweep that draws the tags from the given uniforms [B][N].
+hipError_t launch_full_forward(int dtype, const void* phi, const int32_t* lengths, int B, int N, int T, float* ua,
+                               float* ub, double* Oa, double* Ob, hipStream_t st);
+hipError_t launch_backward_sample(int dtype, const void* phi, const int32_t* lengths, const float* ua,
+                                  const float* uniforms, int B, int N, int T, int32_t* tags, hipStream_t st);
 // Structured potentials (emit [B][N][T] + trans [T][T], float, phi unused) are served for these T.
 bool structured_supported(int T);
 

@@ -269,7 +269,8 @@ __global__ __launch_bounds__(64) void wave_half_kernel(ChainArgs a) {
     if (sp.empty) return;
     const int b = sp.b, N = a.N, T = a.T;
     const int p0 = sp.p0, e = sp.e;
-    const int h = meeting_point(p0, e);
+    const int h = forward_end(a, p0, e);
+    if (a.full_forward && dir == 1) return;
     const size_t TT = (size_t)T * T, vb = (size_t)b * N;
     const TIN* phib = static_cast<const TIN*>(a.phi) + (size_t)b * N * TT;
     const bool exact_only = a.exact_only != 0;
