@@ -77,7 +77,7 @@ typedef enum {
 
 typedef enum {
     LCCRF_OK = 0,
-    LCCRF_EINVAL = -1,     /* bad B, N, T, dtype, op or algo */
+    LCCRF_EINVAL = -1,     /* bad B, N, T (1 <= T <= 256, B * N < 2e9), dtype, op or algo */
     LCCRF_ENULL = -2,      /* a required pointer is NULL */
     LCCRF_EWORKSPACE = -3, /* workspace NULL or smaller than lccrf_workspace_bytes */
     LCCRF_EALIGN = -4,     /* phi, an output or the workspace is misaligned */

@@ -62,7 +62,8 @@ inline MaxWorkspace max_workspace(size_t B, size_t N, size_t T) {
 inline bool shape_ok(int B, int N, int T) {
     if (B < 1 || N < 1 || T < 1 || T > LCCRF_MAX_T) return false;
     const double pots = (double)B * (double)N * (double)T * (double)T;
-    return pots < 4.0e18;
+    // launches use up to 2 * B * ceil(N / 4) workgroups in a 32-bit grid dimension
+    return pots < 4.0e18 && (double)B * (double)N < 2.0e9;
 }
 inline bool dtype_ok(int dt) { return dt == LCCRF_F32 || dt == LCCRF_BF16; }
 inline bool aligned_to(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
