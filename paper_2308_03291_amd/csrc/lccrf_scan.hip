@@ -33,6 +33,11 @@ typedef double f64x4 __attribute__((ext_vector_type(4)));
 constexpr double kTiny = 0x1p-900;  // smallest accepted entry of a linear-domain product
 constexpr int kScanPF = 8;
 
+// Value of lane `src_lane` (any lane, computed per lane).
+__device__ __forceinline__ float lane_bperm(float x, int src_lane) {
+    return __int_as_float(__builtin_amdgcn_ds_bpermute(src_lane << 2, __float_as_int(x)));
+}
+
 struct ScanArgs {
     const void* phi;
     const int32_t* lengths;
@@ -246,7 +251,6 @@ __global__ __launch_bounds__(64) void chunk_product_kernel(ScanArgs a) {
 // next through LDS.
 template <typename TIN>
 __global__ __launch_bounds__(64) void chunk_boundary_kernel(ScanArgs a) {
-    __shared__ __attribute__((aligned(16))) float vec[2][16];
     const int lane = threadIdx.x, o = lane >> 2, q = lane & 3;
     const int b = blockIdx.x >> 1, dir = blockIdx.x & 1;
     const int T = a.T, N = a.N;
@@ -259,7 +263,6 @@ __global__ __launch_bounds__(64) void chunk_boundary_kernel(ScanArgs a) {
     if (dir == 1 && !a.with_beta) return;
     const int Cb = (L + a.chunk - 1) / a.chunk;
     const size_t cb = (size_t)b * a.C;
-    int buf = 0;
     double O = 0.0;
 
     if (dir == 0) {
@@ -267,8 +270,6 @@ __global__ __launch_bounds__(64) void chunk_boundary_kernel(ScanArgs a) {
         float v = (lane < T) ? Elem<TIN>::get(phib + lane) * kLog2e : LCCRF_NEG_INF;  // alpha_0
         float d = finite_or_zero(xor_max<1, 64>(v));
         O = (double)d;
-        if (lane < 16) vec[0][lane] = v - d;
-        __syncthreads();
         float pm[kScanPF][4], rl[kScanPF][4];
         double bs[kScanPF];
         auto load = [&](int c, int slot) {
@@ -278,35 +279,37 @@ __global__ __launch_bounds__(64) void chunk_boundary_kernel(ScanArgs a) {
             rl[slot][0] = e.x; rl[slot][1] = e.y; rl[slot][2] = e.z; rl[slot][3] = e.w;
             bs[slot] = a.base[cb + c];
         };
-        float nv = v - d;
+        // The vector travels from step to step in registers: entry t of the new vector sits in lanes
+        // 4t .. 4t+3, lane (o, q) fetches entries 4q .. 4q+3 with four lane reads.  It is normalised by
+        // the maximum of the PREVIOUS vector (one step stale: consecutive maxima differ little), so the
+        // wave-wide maximum is off the chain of dependent instructions.
+        float nv = (o < T) ? __shfl(v, o, 64) - d : LCCRF_NEG_INF;  // alpha_0, entry o in lanes 4o .. 4o+3
+        float dprev = 0.f;
         walk<kScanPF>(0, Cb - 1, +1, load, [&](int c, int slot) {
-            const float4 f = *reinterpret_cast<const float4*>(&vec[buf][4 * q]);
-            const float x0 = f.x + (pm[slot][0] + rl[slot][0]), x1 = f.y + (pm[slot][1] + rl[slot][1]);
-            const float x2 = f.z + (pm[slot][2] + rl[slot][2]), x3 = f.w + (pm[slot][3] + rl[slot][3]);
+            const float f0 = lane_bperm(nv, 16 * q), f1 = lane_bperm(nv, 16 * q + 4);
+            const float f2 = lane_bperm(nv, 16 * q + 8), f3 = lane_bperm(nv, 16 * q + 12);
+            const float x0 = f0 + (pm[slot][0] + rl[slot][0]), x1 = f1 + (pm[slot][1] + rl[slot][1]);
+            const float x2 = f2 + (pm[slot][2] + rl[slot][2]), x3 = f3 + (pm[slot][3] + rl[slot][3]);
             const float mx = xor_max<1, 4>(fmaxf(fmaxf(x0, x1), fmaxf(x2, x3)));
             const float mf = finite_or_zero(mx);
             const float s = xor_sum<1, 4>((ex2(x0 - mf) + ex2(x1 - mf)) + (ex2(x2 - mf) + ex2(x3 - mf)));
             const float r = mx + lg2(s);
-            d = finite_or_zero(xor_max<4, 64>(r));
-            O += bs[slot] + (double)d;
-            nv = r - d;
-            buf ^= 1;
-            if (q == 0) {
-                vec[buf][o] = nv;
-                if (o < T) a.Fv[(cb + c) * T + o] = nv;
-            }
+            O += bs[slot] + (double)dprev;
+            nv = r - dprev;
+            dprev = finite_or_zero(xor_max<4, 64>(nv));  // used by the next step
+            if (q == 0 && o < T) a.Fv[(cb + c) * T + o] = nv;
             if (lane == 0) a.OF[cb + c] = O;
-            __syncthreads();
         });
         if (a.logZ || a.logZ64) {
-            // the walk has run at least once (L >= 1): entry t sits in lanes 4t .. 4t+3, count it once
-            const float S = xor_sum<1, 64>(q == 0 ? ex2(nv) : 0.f);
-            if (lane == 0 && a.logZ) a.logZ[b] = (float)((O + (double)lg2(S)) * kLn2);
-            if (lane == 0 && a.logZ64) a.logZ64[b] = (O + (double)lg2(S)) * kLn2;
+            // entry t sits in lanes 4t .. 4t+3: count it once
+            const float S = xor_sum<1, 64>(q == 0 ? ex2(nv - dprev) : 0.f);
+            const double lz = (O + (double)dprev + (double)lg2(S)) * kLn2;
+            if (lane == 0 && a.logZ) a.logZ[b] = (float)lz;
+            if (lane == 0 && a.logZ64) a.logZ64[b] = lz;
         }
     } else {
-        if (lane < 16) vec[0][lane] = (lane < T) ? 0.f : LCCRF_NEG_INF;  // beta at the last position
-        __syncthreads();
+        float nv = (o < T) ? 0.f : LCCRF_NEG_INF;  // beta at the last position, entry o in lanes 4o .. 4o+3
+        float dprev = 0.f;
         float pm[kScanPF][4], rl[kScanPF];
         double bs[kScanPF];
         auto load = [&](int c, int slot) {
@@ -317,21 +320,18 @@ __global__ __launch_bounds__(64) void chunk_boundary_kernel(ScanArgs a) {
             bs[slot] = a.base[cb + c];
         };
         walk<kScanPF>(Cb - 1, 1, -1, load, [&](int c, int slot) {
-            const float4 gq = *reinterpret_cast<const float4*>(&vec[buf][4 * q]);
-            const float x0 = pm[slot][0] + gq.x, x1 = pm[slot][1] + gq.y, x2 = pm[slot][2] + gq.z, x3 = pm[slot][3] + gq.w;
+            const float g0 = lane_bperm(nv, 16 * q), g1 = lane_bperm(nv, 16 * q + 4);
+            const float g2 = lane_bperm(nv, 16 * q + 8), g3 = lane_bperm(nv, 16 * q + 12);
+            const float x0 = pm[slot][0] + g0, x1 = pm[slot][1] + g1, x2 = pm[slot][2] + g2, x3 = pm[slot][3] + g3;
             const float mx = xor_max<1, 4>(fmaxf(fmaxf(x0, x1), fmaxf(x2, x3)));
             const float mf = finite_or_zero(mx);
             const float s = xor_sum<1, 4>((ex2(x0 - mf) + ex2(x1 - mf)) + (ex2(x2 - mf) + ex2(x3 - mf)));
             const float r = mx + lg2(s) + rl[slot];
-            const float d = finite_or_zero(xor_max<4, 64>(r));
-            O += bs[slot] + (double)d;
-            buf ^= 1;
-            if (q == 0) {
-                vec[buf][o] = r - d;
-                if (o < T) a.Gv[(cb + c - 1) * T + o] = r - d;
-            }
+            O += bs[slot] + (double)dprev;
+            nv = r - dprev;
+            dprev = finite_or_zero(xor_max<4, 64>(nv));
+            if (q == 0 && o < T) a.Gv[(cb + c - 1) * T + o] = nv;
             if (lane == 0) a.OG[cb + c - 1] = O;
-            __syncthreads();
         });
     }
 }
@@ -421,7 +421,6 @@ constexpr int kPinWindow = 1024;  // chunks of back-pointers held in LDS at a ti
 
 template <typename TIN>
 __global__ __launch_bounds__(64) void chunk_maxplus_boundary_kernel(MaxScanArgs a) {
-    __shared__ __attribute__((aligned(16))) double vec[2][16];
     __shared__ uint8_t win[kPinWindow * 16];
     const int lane = threadIdx.x, t = lane >> 2, q = lane & 3;
     const int b = blockIdx.x;
@@ -435,22 +434,23 @@ __global__ __launch_bounds__(64) void chunk_maxplus_boundary_kernel(MaxScanArgs 
     const size_t cb = (size_t)b * a.C;
     const double ninf = -__builtin_huge_val();
     const TIN* phib = static_cast<const TIN*>(a.phi) + (size_t)b * N * T * T;
-    if (lane < 16) vec[0][lane] = (lane < T) ? (double)Elem<TIN>::get(phib + lane) : ninf;  // delta_0
-    __syncthreads();
-    int buf = 0;
+    // delta of the last boundary, entry t in lanes 4t .. 4t+3: it travels from step to step in registers
+    double dv = (t < T) ? (double)Elem<TIN>::get(phib + t) : ninf;  // delta_0
     double mm[kScanPF][4];
     auto load = [&](int c, int slot) {
         const double* M = a.Mx + (cb + c) * 256;
 #pragma unroll
         for (int jj = 0; jj < 4; ++jj) mm[slot][jj] = M[(4 * q + jj) * 16 + t];
     };
-    double dv = ninf;
     walk<kScanPF>(0, Cb - 1, +1, load, [&](int c, int slot) {
         double bv = ninf;
         int ba = 0x7fffffff;
+        double in[4];
+#pragma unroll
+        for (int jj = 0; jj < 4; ++jj) in[jj] = __shfl(dv, 16 * q + 4 * jj, 64);
 #pragma unroll
         for (int jj = 0; jj < 4; ++jj) {  // ascending entry tags: the first maximum wins
-            const double val = vec[buf][4 * q + jj] + mm[slot][jj];
+            const double val = in[jj] + mm[slot][jj];
             if (val > bv) { bv = val; ba = 4 * q + jj; }
         }
 #pragma unroll
@@ -460,12 +460,7 @@ __global__ __launch_bounds__(64) void chunk_maxplus_boundary_kernel(MaxScanArgs 
             if (pv > bv || (pv == bv && pa < ba)) { bv = pv; ba = pa; }
         }
         dv = bv;
-        buf ^= 1;
-        if (q == 0) {
-            vec[buf][t] = bv;
-            a.K[(cb + c) * 16 + t] = (uint8_t)(ba == 0x7fffffff ? 0 : ba);
-        }
-        __syncthreads();
+        if (q == 0) a.K[(cb + c) * 16 + t] = (uint8_t)(ba == 0x7fffffff ? 0 : ba);
     });
     // best tag at the last position: first maximum (entry t sits in lanes 4t .. 4t+3)
     double bv = (q == 0 && t < T) ? dv : ninf;
