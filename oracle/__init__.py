@@ -190,6 +190,11 @@ def entropy(phi, lengths=None) -> np.ndarray:
     return cross_entropy(phi, phi, lengths)
 
 
+def kl_divergence(phi_p, phi_q, lengths=None) -> np.ndarray:
+    """KL(p || q) [B] float64 = H(p, q) - H(p) (section "Entropy and KL Divergence")."""
+    return cross_entropy(phi_p, phi_q, lengths) - cross_entropy(phi_p, phi_p, lengths)
+
+
 def sample(phi, uniforms, lengths=None):
     """Forward-filtering backward-sampling with the given uniforms [B, N] (float32 in [0, 1)):
     (tags [B, N] int32 with -1 past the length, margin [B] float64: how far, relative to the total

@@ -432,6 +432,38 @@ def test_cross_entropy_against_enumeration(oracle_mod):
     assert np.abs(kl).max() < 1e-5      # float32 rounding of the shifted copy only
 
 
+def test_kl_divergence_against_enumeration_and_closed_form(oracle_mod):
+    """KL(p || q) = sum_y p(y) [log p(y) - log q(y)] by brute force; for one position it is the
+    KL divergence of two categorical distributions (softmax of the first row); it is not symmetric,
+    never negative, zero for q = p, and +inf where q forbids what p allows."""
+    T, N = 3, 5
+    p = _rand(71, 3, N, T, scale=1.5)
+    q = _rand(72, 3, N, T, scale=1.0)
+    lens = np.array([5, 3, 1], dtype=np.int32)
+    kl = oracle_mod.kl_divergence(p, q, lens)
+    for b, L in enumerate(lens):
+        paths = brute.all_paths(T, int(L))
+        sp = brute.path_scores(p[b].astype(np.float64), int(L), paths)
+        sq = brute.path_scores(q[b].astype(np.float64), int(L), paths)
+        lp = sp - scipy.special.logsumexp(sp)
+        lq = sq - scipy.special.logsumexp(sq)
+        assert kl[b] == pytest.approx((np.exp(lp) * (lp - lq)).sum(), abs=1e-10)
+        assert kl[b] > 0
+    a = p[2, 0, 0].astype(np.float64)
+    c = q[2, 0, 0].astype(np.float64)
+    la, lc = a - scipy.special.logsumexp(a), c - scipy.special.logsumexp(c)
+    assert kl[2] == pytest.approx((np.exp(la) * (la - lc)).sum(), abs=1e-12)
+    assert np.abs(oracle_mod.kl_divergence(p, p, lens)).max() < 1e-12
+    rev = oracle_mod.kl_divergence(q, p, lens)
+    assert np.abs(rev - kl).min() > 1e-3          # generic potentials: the two directions differ
+    forb = q.copy()
+    forb[0, 2, :, 1] = -np.inf
+    out = oracle_mod.kl_divergence(p, forb, lens)
+    assert out[0] == np.inf and np.isfinite(out[1:]).all()
+    # the other way round q's support is a subset of p's: finite
+    assert np.isfinite(oracle_mod.kl_divergence(forb, p, lens)).all()
+
+
 def test_entropy_with_forbidden_edges(oracle_mod):
     """-inf potentials carry no probability and must not poison the sum (0 * -inf)."""
     phi = _rand(67, 1, 5, 3)
