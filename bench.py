@@ -14,7 +14,8 @@ Extra objects in the line:
                 between its passes: algorithmic bytes = (sizeof(phi element) + 4) per potential.
   cpu_baseline  the CPU oracle (as it stands, OpenMP over the batch) timed on this host on a
                 bounded sample of the same workload.
-  other_queries log-partition alone, Viterbi decode, entropy, the log-probability of a path and one sample,
+  other_queries log-partition alone, Viterbi decode, entropy, the log-probability of a path, one sample, and the
+                cross-entropy and KL divergence against a second chain,
                 timed the same way (context).
 """
 from __future__ import annotations
@@ -122,7 +123,7 @@ def main():
     lz = torch.empty(w.B, dtype=torch.float32, device=dev)
     tags = torch.empty(w.B, w.N, dtype=torch.int32, device=dev)
     score = torch.empty(w.B, dtype=torch.float32, device=dev)
-    ws = torch.empty(max(crf.workspace_bytes(op, w.B, w.N, w.T, 0 if esz == 4 else 1) for op in (0, 1, 2, 3, 4, 5)),
+    ws = torch.empty(max(crf.workspace_bytes(op, w.B, w.N, w.T, 0 if esz == 4 else 1) for op in (0, 1, 2, 3, 4, 5, 6)),
                      dtype=torch.uint8, device=dev)
     torch.cuda.synchronize()
     log(f"[bench] inputs resident after {time.perf_counter() - t0:.1f} s")
@@ -190,12 +191,19 @@ def main():
         crf.lccrf_argmax(phi, lens, out=tags, score=score, workspace=ws)   # a path to score: the best one
         path = tags.clamp(min=0)
         uniforms = torch.rand(w.B, w.N, device=dev, generator=torch.Generator(device=dev).manual_seed(1))
+        # a second chain for the two-chain queries: half-scale potentials, in the marginals' buffer when the types agree
+        if esz == 4:
+            phi_q = torch.mul(phi, 0.5, out=mu)
+        else:
+            phi_q = (phi.float() * 0.5).to(phi.dtype)
         for name, fn, bpp in (
                 ("log_partition", lambda: crf.lccrf_log_partition(phi, lens, out=lz, workspace=ws), esz),
                 ("argmax", lambda: crf.lccrf_argmax(phi, lens, out=tags, score=score, workspace=ws), esz),
                 ("entropy", lambda: crf.lccrf_entropy(phi, lens, out=score, workspace=ws), esz),
                 ("log_prob", lambda: crf.lccrf_log_prob(phi, path, lens, out=score, workspace=ws), esz),
-                ("sample", lambda: crf.lccrf_sample(phi, uniforms, lens, out=tags, workspace=ws), esz)):
+                ("sample", lambda: crf.lccrf_sample(phi, uniforms, lens, out=tags, workspace=ws), esz),
+                ("cross_entropy", lambda: crf.lccrf_cross_entropy(phi, phi_q, lens, out=score, workspace=ws), 3 * esz),
+                ("kl_divergence", lambda: crf.lccrf_kl_divergence(phi, phi_q, lens, out=score, workspace=ws), 3 * esz)):
             for _ in range(2):
                 fn()
             evs = new_events(2 * max(5, args.steps // 2))

@@ -56,7 +56,8 @@ typedef enum {
     LCCRF_OP_ARGMAX = 2,
     LCCRF_OP_LOG_PROB = 3,
     LCCRF_OP_ENTROPY = 4,
-    LCCRF_OP_SAMPLE = 5
+    LCCRF_OP_SAMPLE = 5,
+    LCCRF_OP_CROSS_ENTROPY = 6, /* also the workspace of lccrf_kl_divergence */
 } lccrf_op;
 
 /* How the recursion over positions is scheduled.  Results are the same up to
@@ -177,6 +178,26 @@ int lccrf_log_prob(const void* phi, lccrf_dtype dt, const int32_t* lengths, cons
  */
 int lccrf_entropy(const void* phi, lccrf_dtype dt, const int32_t* lengths, int B, int N, int T,
                   float* entropy, void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Cross-entropy H(p, q) = -sum_y p(y) log q(y) = logZ_q - sum_e p(e) phi_q(e) and Kullback-Leibler
+ * divergence KL(p || q) = H(p, q) - H(p) of two chains over the same sequences, in nats (paper,
+ * section "Entropy and KL Divergence").  phi_p and phi_q have the same shape, type and lengths.
+ * Neither forms the marginals: one forward-backward read of phi_q gives logZ_q, then the two half
+ * chains of p carry the expected score under phi_q (for KL: the expected score difference
+ * phi_p - phi_q, formed per edge, so close chains lose no digits) while reading both tensors once.
+ * An edge of probability zero under p contributes nothing whatever phi_q holds there; an edge
+ * that p can take and q forbids (-inf) gives +inf.
+ *   out       [B] float32 (device).  Empty chain: 0.  No finite path under p: NaN.
+ * Workspace: lccrf_workspace_bytes(LCCRF_OP_CROSS_ENTROPY, ...).  Errors as lccrf_log_partition
+ * (phi_q is checked like phi).
+ */
+int lccrf_cross_entropy(const void* phi_p, const void* phi_q, lccrf_dtype dt, const int32_t* lengths,
+                        int B, int N, int T, float* out,
+                        void* workspace, size_t workspace_bytes, void* stream);
+int lccrf_kl_divergence(const void* phi_p, const void* phi_q, lccrf_dtype dt, const int32_t* lengths,
+                        int B, int N, int T, float* out,
+                        void* workspace, size_t workspace_bytes, void* stream);
 
 /*
  * One sample per sequence by forward-filtering backward-sampling (paper, section "Sampling a

@@ -23,14 +23,15 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "liblccrf.so")
 
 LCCRF_F32, LCCRF_BF16 = 0, 1
-OP_LOGZ, OP_MARGINALS, OP_ARGMAX, OP_LOG_PROB, OP_ENTROPY, OP_SAMPLE = 0, 1, 2, 3, 4, 5
+OP_LOGZ, OP_MARGINALS, OP_ARGMAX, OP_LOG_PROB, OP_ENTROPY, OP_SAMPLE, OP_CROSS_ENTROPY = 0, 1, 2, 3, 4, 5, 6
 ALGO_AUTO, ALGO_SEQUENTIAL, ALGO_SCAN, ALGO_SEQUENTIAL_EXACT = 0, 1, 2, 3
 MAX_T = 256
 
 EXPORTS = (
     "lccrf_workspace_bytes", "lccrf_log_partition", "lccrf_marginals", "lccrf_argmax",
     "lccrf_log_partition_algo", "lccrf_marginals_algo", "lccrf_argmax_algo",
-    "lccrf_marginals_timed", "lccrf_log_prob", "lccrf_entropy", "lccrf_sample", "lccrf_log_partition_structured",
+    "lccrf_marginals_timed", "lccrf_log_prob", "lccrf_entropy", "lccrf_cross_entropy", "lccrf_kl_divergence",
+    "lccrf_sample", "lccrf_log_partition_structured",
     "lccrf_marginals_structured", "lccrf_argmax_structured", "lccrf_set_scan_chunk", "lccrf_strerror",
     "lccrf_version",
 )
@@ -73,6 +74,9 @@ def load_library() -> ctypes.CDLL:
     lib.lccrf_log_prob.restype = i
     lib.lccrf_entropy.argtypes = base + [vp, vp, sz, vp]
     lib.lccrf_entropy.restype = i
+    for n in ("lccrf_cross_entropy", "lccrf_kl_divergence"):
+        getattr(lib, n).argtypes = [vp, vp, i, vp, i, i, i, vp, vp, sz, vp]
+        getattr(lib, n).restype = i
     lib.lccrf_sample.argtypes = [vp, i, vp, vp, i, i, i, vp, vp, sz, vp]
     lib.lccrf_sample.restype = i
     sbase = [vp, vp, vp, i, i, i]
@@ -230,6 +234,33 @@ def lccrf_entropy(phi: torch.Tensor, lengths: Optional[torch.Tensor] = None, *,
                                out.data_ptr(), ws.data_ptr(), nws, _stream(phi.device))
     _check(rc, "lccrf_entropy")
     return out
+
+
+def _two_chains(name, phi_p, phi_q, lengths, out, workspace):
+    lib = load_library()
+    dt, B, N, T = _phi_args(phi_p)
+    if _phi_args(phi_q) != (dt, B, N, T) or phi_q.device != phi_p.device:
+        raise LccrfError("phi_q must have phi_p's shape, dtype and device")
+    ws, nws = _workspace(OP_CROSS_ENTROPY, B, N, T, dt, phi_p.device, workspace)
+    if out is None:
+        out = torch.empty(B, dtype=torch.float32, device=phi_p.device)
+    with torch.cuda.device(phi_p.device):
+        rc = getattr(lib, name)(phi_p.data_ptr(), phi_q.data_ptr(), dt, _len_ptr(lengths, B, phi_p.device), B, N, T,
+                                out.data_ptr(), ws.data_ptr(), nws, _stream(phi_p.device))
+    _check(rc, name)
+    return out
+
+
+def lccrf_cross_entropy(phi_p: torch.Tensor, phi_q: torch.Tensor, lengths: Optional[torch.Tensor] = None, *,
+                        out: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """Cross-entropy H(p, q) [B] float32 (nats) of the chains of phi_p against those of phi_q."""
+    return _two_chains("lccrf_cross_entropy", phi_p, phi_q, lengths, out, workspace)
+
+
+def lccrf_kl_divergence(phi_p: torch.Tensor, phi_q: torch.Tensor, lengths: Optional[torch.Tensor] = None, *,
+                        out: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """Kullback-Leibler divergence KL(p || q) [B] float32 (nats)."""
+    return _two_chains("lccrf_kl_divergence", phi_p, phi_q, lengths, out, workspace)
 
 
 def lccrf_sample(phi: torch.Tensor, uniforms: torch.Tensor, lengths: Optional[torch.Tensor] = None, *,

@@ -15,7 +15,7 @@ int g_scan_chunk = kDefaultScanChunk;
 struct SumWorkspace {
     size_t ua, ub, Oa, Ob, mail, failed;
     size_t Pl, rel, base, Fv, OF, Gv, OG;  // chunked scan (T <= 16 only, else empty)
-    size_t lz64, ha, hb;                   // log-probability and entropy queries
+    size_t lz64, ha, hb, hoff;             // log-probability, entropy and cross-entropy queries
     size_t total;
 };
 inline SumWorkspace sum_workspace(size_t B, size_t N, size_t T) {
@@ -38,6 +38,7 @@ inline SumWorkspace sum_workspace(size_t B, size_t N, size_t T) {
     w.lz64 = off; off += round_up(B * sizeof(double));
     w.ha = off; off += round_up(B * T * sizeof(float));
     w.hb = off; off += round_up(B * T * sizeof(float));
+    w.hoff = off; off += round_up(B * 2 * sizeof(double));
     w.total = off;
     return w;
 }
@@ -142,7 +143,8 @@ size_t lccrf_workspace_bytes(lccrf_op op, int B, int N, int T, lccrf_dtype dt) {
         case LCCRF_OP_MARGINALS:
         case LCCRF_OP_LOG_PROB:
         case LCCRF_OP_ENTROPY:
-        case LCCRF_OP_SAMPLE: return sum_workspace(B, N, T).total;
+        case LCCRF_OP_SAMPLE:
+        case LCCRF_OP_CROSS_ENTROPY: return sum_workspace(B, N, T).total;
         case LCCRF_OP_ARGMAX: return max_workspace(B, N, T).total;
         default: return 0;
     }
@@ -211,6 +213,22 @@ int lccrf_argmax(const void* phi, lccrf_dtype dt, const int32_t* lengths, int B,
                              LCCRF_ALGO_AUTO);
 }
 
+// log Z [B] in double precision into the workspace's lz64 slot, by the schedule AUTO would take.
+static hipError_t launch_log_partition64(const void* phi, int dt, const int32_t* lengths, int B, int N, int T,
+                                         const SumWorkspace& w, char* base, hipStream_t st) {
+    double* lz64 = reinterpret_cast<double*>(base + w.lz64);
+    if (scan_pays(B, N, T))
+        return lccrf::launch_scan_boundaries(
+            dt, phi, lengths, B, N, T, g_scan_chunk, reinterpret_cast<float*>(base + w.Pl),
+            reinterpret_cast<float*>(base + w.rel), reinterpret_cast<double*>(base + w.base),
+            reinterpret_cast<float*>(base + w.Fv), reinterpret_cast<double*>(base + w.OF),
+            reinterpret_cast<float*>(base + w.Gv), reinterpret_cast<double*>(base + w.OG), nullptr, false, st, lz64);
+    return lccrf::launch_sequential_sum(0, dt, phi, lengths, B, N, T, reinterpret_cast<float*>(base + w.ua),
+                                        reinterpret_cast<float*>(base + w.ub), reinterpret_cast<double*>(base + w.Oa),
+                                        reinterpret_cast<double*>(base + w.Ob), nullptr, nullptr, st, nullptr, false,
+                                        nullptr, nullptr, lz64);
+}
+
 int lccrf_log_prob(const void* phi, lccrf_dtype dt, const int32_t* lengths, const int32_t* tags, int B, int N, int T,
                    float* log_prob, void* workspace, size_t workspace_bytes, void* stream) {
     const size_t need = lccrf_workspace_bytes(LCCRF_OP_LOG_PROB, B, N, T, dt);
@@ -222,18 +240,7 @@ int lccrf_log_prob(const void* phi, lccrf_dtype dt, const int32_t* lengths, cons
     char* base = static_cast<char*>(workspace);
     hipStream_t st = static_cast<hipStream_t>(stream);
     double* lz64 = reinterpret_cast<double*>(base + w.lz64);
-    hipError_t e;
-    if (scan_pays(B, N, T))
-        e = lccrf::launch_scan_boundaries(dt, phi, lengths, B, N, T, g_scan_chunk, reinterpret_cast<float*>(base + w.Pl),
-                                          reinterpret_cast<float*>(base + w.rel), reinterpret_cast<double*>(base + w.base),
-                                          reinterpret_cast<float*>(base + w.Fv), reinterpret_cast<double*>(base + w.OF),
-                                          reinterpret_cast<float*>(base + w.Gv), reinterpret_cast<double*>(base + w.OG),
-                                          nullptr, false, st, lz64);
-    else
-        e = lccrf::launch_sequential_sum(0, dt, phi, lengths, B, N, T, reinterpret_cast<float*>(base + w.ua),
-                                         reinterpret_cast<float*>(base + w.ub), reinterpret_cast<double*>(base + w.Oa),
-                                         reinterpret_cast<double*>(base + w.Ob), nullptr, nullptr, st, nullptr, false,
-                                         nullptr, nullptr, lz64);
+    hipError_t e = launch_log_partition64(phi, dt, lengths, B, N, T, w, base, st);
     if (e == hipSuccess) e = lccrf::launch_path_log_prob(dt, phi, lengths, tags, B, N, T, lz64, log_prob, st);
     return e == hipSuccess ? LCCRF_OK : LCCRF_ELAUNCH;
 }
@@ -253,6 +260,37 @@ int lccrf_entropy(const void* phi, lccrf_dtype dt, const int32_t* lengths, int B
         reinterpret_cast<float*>(base + w.ha), reinterpret_cast<float*>(base + w.hb), entropy,
         static_cast<hipStream_t>(stream));
     return e == hipSuccess ? LCCRF_OK : LCCRF_ELAUNCH;
+}
+
+static int cross_query(bool kl, const void* phi_p, const void* phi_q, lccrf_dtype dt, const int32_t* lengths, int B, int N,
+                       int T, float* out, void* workspace, size_t workspace_bytes, void* stream) {
+    const size_t need = lccrf_workspace_bytes(LCCRF_OP_CROSS_ENTROPY, B, N, T, dt);
+    const int rc = check_common(phi_p, dt, B, N, T, workspace, workspace_bytes, need, LCCRF_ALGO_AUTO);
+    if (rc != LCCRF_OK) return rc;
+    if (!phi_q || !out) return LCCRF_ENULL;
+    if (!aligned_to(phi_q, 16) || !aligned_to(out, 4) || (lengths && !aligned_to(lengths, 4))) return LCCRF_EALIGN;
+    const SumWorkspace w = sum_workspace(B, N, T);
+    char* base = static_cast<char*>(workspace);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    // log Z_q first: the chains of p then reuse the vectors' storage, the double-precision result stays
+    hipError_t e = launch_log_partition64(phi_q, dt, lengths, B, N, T, w, base, st);
+    if (e == hipSuccess)
+        e = lccrf::launch_cross(kl, dt, phi_p, phi_q, lengths, B, N, T, reinterpret_cast<float*>(base + w.ua),
+                                reinterpret_cast<float*>(base + w.ub), reinterpret_cast<double*>(base + w.Oa),
+                                reinterpret_cast<double*>(base + w.Ob), reinterpret_cast<float*>(base + w.ha),
+                                reinterpret_cast<float*>(base + w.hb), reinterpret_cast<double*>(base + w.hoff),
+                                reinterpret_cast<const double*>(base + w.lz64), out, st);
+    return e == hipSuccess ? LCCRF_OK : LCCRF_ELAUNCH;
+}
+
+int lccrf_cross_entropy(const void* phi_p, const void* phi_q, lccrf_dtype dt, const int32_t* lengths, int B, int N, int T,
+                        float* out, void* workspace, size_t workspace_bytes, void* stream) {
+    return cross_query(false, phi_p, phi_q, dt, lengths, B, N, T, out, workspace, workspace_bytes, stream);
+}
+
+int lccrf_kl_divergence(const void* phi_p, const void* phi_q, lccrf_dtype dt, const int32_t* lengths, int B, int N, int T,
+                        float* out, void* workspace, size_t workspace_bytes, void* stream) {
+    return cross_query(true, phi_p, phi_q, dt, lengths, B, N, T, out, workspace, workspace_bytes, stream);
 }
 
 int lccrf_sample(const void* phi, lccrf_dtype dt, const int32_t* lengths, const float* uniforms, int B, int N, int T,
@@ -349,6 +387,6 @@ int lccrf_set_scan_chunk(int chunk) {
     return LCCRF_OK;
 }
 
-int lccrf_version(void) { return 104; }
+int lccrf_version(void) { return 105; }
 
 }  // extern "C"

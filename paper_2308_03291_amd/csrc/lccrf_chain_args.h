@@ -36,6 +36,10 @@ struct ChainArgs {
     // the path behind them given the current tag, and leave it here for the meeting position.
     float* ha;  // [B][T] H(y_0 .. y_{h-1} | y_h = t), base-2
     float* hb;  // [B][T] H(y_{h+1} .. y_{L-1} | y_h = t), base-2
+    // Cross-entropy and KL divergence (psi non-null): ha and hb carry the conditional expectation of
+    // the score under psi (of the score difference) instead, natural units, each less a common offset.
+    const void* psi;  // potentials of the second chain, same layout and type as phi
+    double* hoff;     // [B][2] the offsets of ha and hb
     // Structured potentials (emit non-null; float only, T <= 64, whole sequences): phi is not read,
     // phi[b][i][s][t] = trans[s][t] + emit[b][i][t].
     const float* emit;   // [B][N][T]

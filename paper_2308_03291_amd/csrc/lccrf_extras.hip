@@ -108,13 +108,22 @@ static hipError_t launch_entropy_combine(const ChainArgs& a, float* H, hipStream
 
 
 // ---------------------------------------------------------------------------------------
-// Entropy first pass for T > 32 (the one-wave kernels carry it themselves for T <= 32).
+// Expectations carried along the half chains: entropy first pass for T > 32 (the one-wave
+// kernels carry it themselves for T <= 32), and the expected score difference behind the
+// cross-entropy and the Kullback-Leibler divergence of two chains (any T).
 //
-// The same two half chains as chain_half_kernel, each carrying besides its normalised vector
-// the conditional entropy (base 2) of the path behind it given the current tag:
-//     forward:  h_i(t) = sum_s q(s|t) [h_{i-1}(s) - log2 q(s|t)],  q(s|t) = 2^(ua(s) + phi2(s,t)) / S(t)
-//     backward: h_{i-1}(s) = sum_t q(t|s) [h_i(t) - log2 q(t|s)],  q(t|s) = 2^(phi2(s,t) + ub(t)) / S(s)
-// evaluated as U / S + log2 S with U = sum e (h - log2 e) over the shifted exponentials e.
+// The same two half chains as chain_half_kernel, each carrying besides its normalised vector a
+// second vector h: the conditional expectation, given the current tag, of a quantity summed over
+// the path behind it.  With q(s|t) = 2^(ua(s) + phi2(s,t)) / S(t) on the forward chain
+// (q(t|s) = 2^(phi2(s,t) + ub(t)) / S(s) on the backward chain):
+//     MODE 0, entropy (base 2):   h_i(t) = sum_s q(s|t) [h_{i-1}(s) - log2 q(s|t)],
+//                                 evaluated as U / S + log2 S with U = sum e (h - log2 e);
+//     MODE 1, cross-entropy:      h_i(t) = sum_s q(s|t) [h_{i-1}(s) + psi_i(s,t)],
+//     MODE 2, KL divergence:      h_i(t) = sum_s q(s|t) [h_{i-1}(s) + phi_i(s,t) - psi_i(s,t)],
+// psi being the potentials of the second chain (natural units), read beside phi; an edge of
+// weight zero contributes nothing whatever psi holds there.  In modes 1 and 2 a common shift of
+// h (its largest finite entry) moves into a double-precision offset at every step, so the vector
+// stays small however long the chain is.
 // Plain exact steps (every sum against its own maximum), a secondary query: the forward step
 // takes the column maxima through LDS first, then the sums.
 template <typename G>
@@ -127,11 +136,30 @@ struct EntropySmem {
     alignas(16) float wmax[2][16];
 };
 
+template <typename TIN, bool ALIGNED>
+__device__ __forceinline__ void load_row4(const TIN* __restrict__ mat, int T, int c4, int s, float (&o)[4]) {
+    const TIN* row = mat + (size_t)(s < T ? s : T - 1) * T;
+    if (ALIGNED) {
+        Elem<TIN>::get4(row + (c4 < T ? c4 : T - 4), o);
+    } else {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) o[j] = Elem<TIN>::get(row + (c4 + j < T ? c4 + j : T - 1));
+    }
+}
 
-template <typename G, typename TIN, bool ALIGNED>
+__device__ __forceinline__ float expectation_of(float U, float S) { return S > 0.f ? U / S : 0.f; }
+
+template <typename G, typename TIN, bool ALIGNED, int MODE>
 __global__ __launch_bounds__(G::W) void entropy_half_kernel(ChainArgs a) {
     __shared__ EntropySmem<G> sm;
     constexpr int ITEMS = G::ITEMS, PF = 2;
+    constexpr bool CROSS = MODE != 0;
+    // the second tile travels through a ring of its own where registers allow (QRING); the
+    // sixteen-wave geometries have 128 registers a thread: there its rows are fetched where they
+    // are used
+    constexpr bool LATE_PSI = CROSS && G::WAVES >= 16;
+    constexpr bool QRING = CROSS && !LATE_PSI;
+    constexpr int QITEMS = QRING ? ITEMS : 1, QPF = QRING ? PF : 1;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int b = blockIdx.x >> 1, dir = blockIdx.x & 1;
     const int N = a.N, T = a.T;
@@ -141,6 +169,7 @@ __global__ __launch_bounds__(G::W) void entropy_half_kernel(ChainArgs a) {
     const int c4 = 4 * (tid % G::LPR), r0 = tid / G::LPR;
     const size_t TT = (size_t)T * T, vb = (size_t)b * N;
     const TIN* phib = static_cast<const TIN*>(a.phi) + (size_t)b * N * TT;
+    const TIN* psib = CROSS ? static_cast<const TIN*>(a.psi) + (size_t)b * N * TT : phib;
 
     for (int k = tid; k < 2 * G::TCAP; k += G::W) {
         (&sm.rvec[0][0])[k] = LCCRF_NEG_INF;
@@ -148,34 +177,71 @@ __global__ __launch_bounds__(G::W) void entropy_half_kernel(ChainArgs a) {
     }
     if (tid < 32) (&sm.wmax[0][0])[tid] = LCCRF_NEG_INF;
     __syncthreads();
-    if (tid < T) sm.rvec[0][tid] = dir == 0 ? Elem<TIN>::get(phib + tid) * kLog2e : 0.f;
+    if (tid < T) {
+        const float p0 = Elem<TIN>::get(phib + tid);
+        sm.rvec[0][tid] = dir == 0 ? p0 * kLog2e : 0.f;
+        if (CROSS && dir == 0 && p0 != LCCRF_NEG_INF) {  // the score of the first tag belongs to the forward chain
+            const float q0 = Elem<TIN>::get(psib + tid);
+            sm.hvec[0][tid] = MODE == 1 ? q0 : p0 - q0;
+        }
+    }
     __syncthreads();
 
     float ring[PF][ITEMS][4];
-    auto load = [&](int i, int slot) { load_tile<G, TIN, ALIGNED>(phib + (size_t)i * TT, T, c4, r0, ring[slot]); };
-    double O = 0.0;
+    float qring[QPF][QITEMS][4];
+    auto load = [&](int i, int slot) {
+        load_tile<G, TIN, ALIGNED>(phib + (size_t)i * TT, T, c4, r0, ring[slot]);
+        if constexpr (QRING) load_tile<G, TIN, ALIGNED>(psib + (size_t)i * TT, T, c4, r0, qring[slot]);
+    };
+    // what an edge adds to the carried expectation (modes 1 and 2)
+    auto edge_term = [&](int i, int slot, int k, const float (&x)[4], float (&f)[4]) {
+        float qv[4];
+        if constexpr (LATE_PSI) {
+            load_row4<TIN, ALIGNED>(psib + (size_t)i * TT, T, c4, r0 + k * G::RPP, qv);
+        } else {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) qv[j] = qring[QRING ? slot : 0][QRING ? k : 0][j];
+        }
+#pragma unroll
+        for (int j = 0; j < 4; ++j) f[j] = MODE == 1 ? qv[j] : x[j] - qv[j];
+    };
+    double O = 0.0, Hoff = 0.0;
     int buf = 0;
     auto shift = [&]() {  // normaliser of the vector in rvec[buf]: its maximum, by every thread
         float d = LCCRF_NEG_INF;
         for (int t = lane; t < T; t += 64) d = fmaxf(d, sm.rvec[buf][t]);
         return finite_or_zero(xor_max<1, 64>(d));
     };
+    auto hshift = [&]() {  // largest finite entry of hvec[buf] (0 if there is none), by every thread
+        float d = LCCRF_NEG_INF;
+        for (int t = lane; t < T; t += 64) {
+            const float g = sm.hvec[buf][t];
+            if (fabsf(g) < __builtin_huge_valf()) d = fmaxf(d, g);
+        }
+        return finite_or_zero(xor_max<1, 64>(d));
+    };
 
     if (dir == 0) {
-        walk<PF>(1, h, +1, load, [&](int, int slot) {
+        walk<PF>(1, h, +1, load, [&](int i, int slot) {
             float (&x)[ITEMS][4] = ring[slot];
             const float d = shift();
             O += (double)d;
+            float c = 0.f;
+            if (CROSS) {
+                c = hshift();
+                Hoff += (double)c;
+            }
             float ua[ITEMS], hin[ITEMS], lm[4] = {LCCRF_NEG_INF, LCCRF_NEG_INF, LCCRF_NEG_INF, LCCRF_NEG_INF};
 #pragma unroll
             for (int k = 0; k < ITEMS; ++k) {
                 const int s = r0 + k * G::RPP;
                 ua[k] = (s < T) ? sm.rvec[buf][s] - d : LCCRF_NEG_INF;
-                hin[k] = (s < T) ? sm.hvec[buf][s] : 0.f;
+                hin[k] = (s < T) ? sm.hvec[buf][s] - c : 0.f;
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
-                    x[k][j] = __builtin_fmaf(x[k][j], kLog2e, ua[k]);
-                    lm[j] = fmaxf(lm[j], x[k][j]);
+                    const float xs = __builtin_fmaf(x[k][j], kLog2e, ua[k]);
+                    if (!CROSS) x[k][j] = xs;  // the raw potential is needed again in mode 2
+                    lm[j] = fmaxf(lm[j], xs);
                 }
             }
 #pragma unroll
@@ -191,14 +257,18 @@ __global__ __launch_bounds__(G::W) void entropy_half_kernel(ChainArgs a) {
                 M[j] = finite_or_zero(M[j]);
             }
 #pragma unroll
-            for (int k = 0; k < ITEMS; ++k)
+            for (int k = 0; k < ITEMS; ++k) {
+                float f[4] = {0.f, 0.f, 0.f, 0.f};
+                if constexpr (CROSS) edge_term(i, slot, k, x[k], f);
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
-                    const float arg = x[k][j] - M[j];
+                    const float arg = (CROSS ? __builtin_fmaf(x[k][j], kLog2e, ua[k]) : x[k][j]) - M[j];
                     const float ex = ex2(arg);
                     ls[j] += ex;
-                    lu[j] = __builtin_fmaf(ex, hin[k] - log2_term(arg), lu[j]);
+                    if (CROSS) lu[j] += ex > 0.f ? ex * (hin[k] + f[j]) : 0.f;
+                    else lu[j] = __builtin_fmaf(ex, hin[k] - log2_term(arg), lu[j]);
                 }
+            }
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
                 ls[j] = xor_sum<G::LPR, 64>(ls[j]);
@@ -218,24 +288,31 @@ __global__ __launch_bounds__(G::W) void entropy_half_kernel(ChainArgs a) {
                     Mt = fmaxf(Mt, sm.pmax[w][tid]);
                 }
                 sm.rvec[buf ^ 1][tid] = Mt + lg2(S);  // Mt = -inf gives S = 0: -inf
-                sm.hvec[buf ^ 1][tid] = entropy_of(U, S);
+                sm.hvec[buf ^ 1][tid] = CROSS ? expectation_of(U, S) : entropy_of(U, S);
             }
             __syncthreads();
             buf ^= 1;
         });
     } else {
-        walk<PF>(e, h + 1, -1, load, [&](int, int slot) {
+        walk<PF>(e, h + 1, -1, load, [&](int i, int slot) {
             float (&y)[ITEMS][4] = ring[slot];
             const float d = shift();
             O += (double)d;
+            float c = 0.f;
+            if (CROSS) {
+                c = hshift();
+                Hoff += (double)c;
+            }
             float ub[4], hin[4];
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
                 ub[j] = (c4 + j < T) ? sm.rvec[buf][c4 + j] - d : LCCRF_NEG_INF;
-                hin[j] = (c4 + j < T) ? sm.hvec[buf][c4 + j] : 0.f;
+                hin[j] = (c4 + j < T) ? sm.hvec[buf][c4 + j] - c : 0.f;
             }
 #pragma unroll
             for (int k = 0; k < ITEMS; ++k) {
+                float f[4] = {0.f, 0.f, 0.f, 0.f};
+                if constexpr (CROSS) edge_term(i, slot, k, y[k], f);
 #pragma unroll
                 for (int j = 0; j < 4; ++j) y[k][j] = __builtin_fmaf(y[k][j], kLog2e, ub[j]);
                 const float m = xor_max<1, G::LPR>(fmaxf(fmaxf(y[k][0], y[k][1]), fmaxf(y[k][2], y[k][3])));
@@ -246,13 +323,14 @@ __global__ __launch_bounds__(G::W) void entropy_half_kernel(ChainArgs a) {
                     const float arg = y[k][j] - g;
                     const float ex = ex2(arg);
                     Sl += ex;
-                    Ul = __builtin_fmaf(ex, hin[j] - log2_term(arg), Ul);
+                    if (CROSS) Ul += ex > 0.f ? ex * (hin[j] + f[j]) : 0.f;
+                    else Ul = __builtin_fmaf(ex, hin[j] - log2_term(arg), Ul);
                 }
                 const float S = xor_sum<1, G::LPR>(Sl), U = xor_sum<1, G::LPR>(Ul);
                 const int s = r0 + k * G::RPP;
                 if (c4 == 0 && s < T) {
                     sm.rvec[buf ^ 1][s] = m + lg2(S);
-                    sm.hvec[buf ^ 1][s] = entropy_of(U, S);
+                    sm.hvec[buf ^ 1][s] = CROSS ? expectation_of(U, S) : entropy_of(U, S);
                 }
             }
             __syncthreads();
@@ -267,18 +345,32 @@ __global__ __launch_bounds__(G::W) void entropy_half_kernel(ChainArgs a) {
         (dir == 0 ? a.ha : a.hb)[(size_t)b * T + tid] = sm.hvec[buf][tid];
     }
     if (tid == 0) (dir == 0 ? a.Oa : a.Ob)[vb + h] = O;
+    if (CROSS && tid == 0) a.hoff[2 * b + dir] = Hoff;
 }
 
-template <typename TIN, bool ALIGNED>
+template <typename TIN, bool ALIGNED, int MODE>
 static hipError_t launch_entropy_T(const ChainArgs& a, hipStream_t st) {
     const dim3 grid(2 * a.B);
-    if (a.T <= 64)
-        hipLaunchKernelGGL((entropy_half_kernel<Geo<16, 4, 4>, TIN, ALIGNED>), grid, dim3(256), 0, st, a);
-    else if (a.T <= 128)
-        hipLaunchKernelGGL((entropy_half_kernel<Geo<32, 16, 4>, TIN, ALIGNED>), grid, dim3(1024), 0, st, a);
-    else
-        hipLaunchKernelGGL((entropy_half_kernel<Geo<64, 16, 16>, TIN, ALIGNED>), grid, dim3(1024), 0, st, a);
+    if (a.T <= 16)
+        hipLaunchKernelGGL((entropy_half_kernel<Geo<4, 1, 1>, TIN, ALIGNED, MODE>), grid, dim3(64), 0, st, a);
+    else if (a.T <= 32)
+        hipLaunchKernelGGL((entropy_half_kernel<Geo<8, 4, 1>, TIN, ALIGNED, MODE>), grid, dim3(256), 0, st, a);
+    else if (a.T <= 64)
+        hipLaunchKernelGGL((entropy_half_kernel<Geo<16, 4, 4>, TIN, ALIGNED, MODE>), grid, dim3(256), 0, st, a);
+    else if (a.T <= 128) {
+        if constexpr (MODE == 0)
+            hipLaunchKernelGGL((entropy_half_kernel<Geo<32, 16, 4>, TIN, ALIGNED, MODE>), grid, dim3(1024), 0, st, a);
+        else  // two tiles in flight: eight waves, so that a thread has the registers for both rings
+            hipLaunchKernelGGL((entropy_half_kernel<Geo<32, 8, 8>, TIN, ALIGNED, MODE>), grid, dim3(512), 0, st, a);
+    } else
+        hipLaunchKernelGGL((entropy_half_kernel<Geo<64, 16, 16>, TIN, ALIGNED, MODE>), grid, dim3(1024), 0, st, a);
     return hipGetLastError();
+}
+template <int MODE>
+static hipError_t launch_entropy_mode(int dtype, const ChainArgs& a, hipStream_t st) {
+    const bool aligned = (a.T % 4) == 0;
+    if (dtype == 0) return aligned ? launch_entropy_T<float, true, MODE>(a, st) : launch_entropy_T<float, false, MODE>(a, st);
+    return aligned ? launch_entropy_T<uint16_t, true, MODE>(a, st) : launch_entropy_T<uint16_t, false, MODE>(a, st);
 }
 
 // H(p) [B] for every sequence: first pass in entropy mode, then the combination at the meeting point.
@@ -287,18 +379,64 @@ hipError_t launch_entropy(int dtype, const void* phi, const int32_t* lengths, in
     ChainArgs a{phi, lengths, B, N, T, ua, ub, Oa, Ob, nullptr, nullptr, 0, nullptr, 0, 1, nullptr, nullptr, nullptr, nullptr};
     a.ha = ha;
     a.hb = hb;
-    hipError_t e;
-    if (wave_supported(T)) {
-        e = launch_wave_pass(false, dtype, a, st);
-    } else {
-        const bool aligned = (T % 4) == 0;
-        if (dtype == 0)
-            e = aligned ? launch_entropy_T<float, true>(a, st) : launch_entropy_T<float, false>(a, st);
-        else
-            e = aligned ? launch_entropy_T<uint16_t, true>(a, st) : launch_entropy_T<uint16_t, false>(a, st);
-    }
+    const hipError_t e = wave_supported(T) ? launch_wave_pass(false, dtype, a, st) : launch_entropy_mode<0>(dtype, a, st);
     if (e != hipSuccess) return e;
     return launch_entropy_combine(a, H, st);
+}
+
+// Cross-entropy H(p, q) = log Z_q - E_p[score_q(y)] (kl = false) or Kullback-Leibler divergence
+// KL(p || q) = E_p[score_p(y) - score_q(y)] - log Z_p + log Z_q (kl = true) of two chains over the
+// same sequences: the expectation from the half chains of p at their meeting position (as the
+// entropy above), log Z_p from the same vectors, log Z_q handed in (double precision, natural
+// logarithm).  No finite path under p: NaN.  One wave per sequence.
+__global__ __launch_bounds__(64) void cross_combine_kernel(ChainArgs a, const double* __restrict__ logZq, float* __restrict__ out,
+                                                           int kl) {
+    const int b = blockIdx.x, lane = threadIdx.x;
+    const int N = a.N, T = a.T;
+    const int L = clamp_length(a.lengths, b, N);
+    if (L == 0) {
+        if (lane == 0) out[b] = 0.f;
+        return;
+    }
+    const int h = meeting_point(0, L - 1);
+    const size_t vb = (size_t)b * N;
+    const float* ua = a.ua + (vb + h) * T;
+    const float* ub = a.ub + (vb + h) * T;
+    float m = LCCRF_NEG_INF;
+    for (int t = lane; t < T; t += 64) m = fmaxf(m, ua[t] + ub[t]);
+    m = xor_max<1, 64>(m);
+    if (m == LCCRF_NEG_INF) {
+        if (lane == 0) out[b] = __builtin_nanf("");
+        return;
+    }
+    float S = 0.f;
+    for (int t = lane; t < T; t += 64) S += ex2(ua[t] + ub[t] - m);
+    S = xor_sum<1, 64>(S);
+    float acc = 0.f;
+    for (int t = lane; t < T; t += 64) {
+        const float p = ex2(ua[t] + ub[t] - m) / S;
+        if (p > 0.f) acc += p * (a.ha[(size_t)b * T + t] + a.hb[(size_t)b * T + t]);
+    }
+    acc = xor_sum<1, 64>(acc);
+    if (lane == 0) {
+        const double E = (double)acc + a.hoff[2 * b] + a.hoff[2 * b + 1];
+        const double lzp = (a.Oa[vb + h] + a.Ob[vb + h] + (double)m + (double)lg2(S)) * kLn2;
+        out[b] = (float)(kl ? E - lzp + logZq[b] : logZq[b] - E);
+    }
+}
+
+hipError_t launch_cross(bool kl, int dtype, const void* phi_p, const void* phi_q, const int32_t* lengths, int B, int N,
+                        int T, float* ua, float* ub, double* Oa, double* Ob, float* ha, float* hb, double* hoff,
+                        const double* logZq, float* out, hipStream_t st) {
+    ChainArgs a{phi_p, lengths, B, N, T, ua, ub, Oa, Ob, nullptr, nullptr, 0, nullptr, 0, 1, nullptr, nullptr, nullptr, nullptr};
+    a.ha = ha;
+    a.hb = hb;
+    a.hoff = hoff;
+    a.psi = phi_q;
+    const hipError_t e = kl ? launch_entropy_mode<2>(dtype, a, st) : launch_entropy_mode<1>(dtype, a, st);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(cross_combine_kernel, dim3(B), dim3(64), 0, st, a, logZq, out, kl ? 1 : 0);
+    return hipGetLastError();
 }
 
 // ---------------------------------------------------------------------------------------

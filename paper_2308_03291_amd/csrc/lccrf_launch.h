@@ -77,4 +77,10 @@ hipError_t launch_chunked_max(int dtype, const void* phi, const int32_t* lengths
 hipError_t launch_entropy(int dtype, const void* phi, const int32_t* lengths, int B, int N, int T, float* ua, float* ub,
                           double* Oa, double* Ob, float* ha, float* hb, float* H, hipStream_t st);
 
+// Cross-entropy H(p, q) (kl false) or KL(p || q) (kl true) [B]: the half chains of phi_p carry the expected
+// score under phi_q (the expected score difference); logZq [B]: log Z of phi_q (natural logarithm); hoff: [B][2] doubles.
+hipError_t launch_cross(bool kl, int dtype, const void* phi_p, const void* phi_q, const int32_t* lengths, int B, int N,
+                        int T, float* ua, float* ub, double* Oa, double* Ob, float* ha, float* hb, double* hoff,
+                        const double* logZq, float* out, hipStream_t st);
+
 }  // namespace lccrf
