@@ -41,6 +41,8 @@ def _load():
     lib.lccrf_oracle_log_prob.restype = i
     lib.lccrf_oracle_cross_entropy.argtypes = [vp, vp, i, ip, i, i, i, dp]
     lib.lccrf_oracle_cross_entropy.restype = i
+    lib.lccrf_oracle_semi_markov_log_partition.argtypes = [vp, i, ip, i, i, i, i, dp]
+    lib.lccrf_oracle_semi_markov_log_partition.restype = i
     lib.lccrf_oracle_sample.argtypes = [vp, i, ip, vp, i, i, i, vp, dp]
     lib.lccrf_oracle_sample.restype = i
     lib.lccrf_oracle_threads.argtypes = []
@@ -193,6 +195,22 @@ def entropy(phi, lengths=None) -> np.ndarray:
 def kl_divergence(phi_p, phi_q, lengths=None) -> np.ndarray:
     """KL(p || q) [B] float64 = H(p, q) - H(p) (section "Entropy and KL Divergence")."""
     return cross_entropy(phi_p, phi_q, lengths) - cross_entropy(phi_p, phi_p, lengths)
+
+
+def semi_markov_log_partition(phi, lengths=None) -> np.ndarray:
+    """logZ [B] float64 of the semi-Markov CRF with potentials phi [B, N, K, T, T] (float32 numpy, or a
+    torch float32 / bfloat16 tensor): phi[b, i, k, s, t] scores a segment tagged t that ends at i
+    and covers k + 1 positions, after a segment tagged s."""
+    lib = _load()
+    arr, dt, shape = _as_storage(phi)
+    B, N, K, T, T2 = shape
+    assert T == T2
+    l = _lengths(lengths, B)
+    out = np.empty((B,))
+    rc = lib.lccrf_oracle_semi_markov_log_partition(_ptr(arr), dt, _ptr(l), B, N, K, T, _ptr(out))
+    if rc != 0:
+        raise RuntimeError(f"oracle error {rc}")
+    return out
 
 
 def sample(phi, uniforms, lengths=None):

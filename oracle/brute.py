@@ -77,3 +77,34 @@ def enumerate_sequence(phi: np.ndarray, L: int):
         plogp = np.where(p > 0, p * (sc - logZ), 0.0)
     return {"logZ": float(logZ), "mu": mu, "path": path, "score": float(sc[best]),
             "gap": float(gap), "entropy": float(-plogp.sum())}
+
+
+def segmentations(L: int, K: int):
+    """All splits of positions 0..L-1 into consecutive segments of 1..K positions, as tuples of
+    segment lengths (compositions of L with parts <= K)."""
+    if L == 0:
+        return [()]
+    out = []
+    for first in range(1, min(K, L) + 1):
+        out += [(first,) + rest for rest in segmentations(L - first, K)]
+    return out
+
+
+def semi_markov_log_partition(phi: np.ndarray, L: int) -> float:
+    """log sum over every labelled segmentation of exp(score), by enumeration.  phi: [N, K, T, T]
+    float64, phi[i][k][s][t] the score of a segment with tag t ending at i, covering k + 1
+    positions, after a segment tagged s (row 0 for the first segment)."""
+    import itertools
+    _, K, T, _ = phi.shape
+    scores = []
+    for seg in segmentations(L, K):
+        ends = np.cumsum(seg) - 1
+        for tags in itertools.product(range(T), repeat=len(seg)):
+            sc, prev = 0.0, 0
+            for e, n, t in zip(ends, seg, tags):
+                sc += phi[e, n - 1, prev, t]
+                prev = t
+            scores.append(sc)
+    scores = np.array(scores)
+    m = scores.max()
+    return float(m + np.log(np.exp(scores - m).sum())) if np.isfinite(m) else float("-inf")

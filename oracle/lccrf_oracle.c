@@ -420,3 +420,53 @@ int lccrf_oracle_threads(void) { return omp_get_max_threads(); }
 #else
 int lccrf_oracle_threads(void) { return 1; }
 #endif
+
+/*
+ * Semi-Markov CRF, log-partition (section "Segmentation with Semi-Markov CRF": the linear chain's
+ * parametrisation with transition matrices, except that a transition may jump over several
+ * positions; forward algorithm in O(K T^2 L) for segments of at most K positions).
+ *
+ * A structure is a split of positions 0..L-1 into consecutive segments of 1..K positions, each
+ * carrying a tag.  phi[b][i][k][s][t] is the log-potential of a segment with tag t that ENDS at
+ * position i and covers k + 1 positions, the segment before it carrying tag s; for the first
+ * segment (k = i) row s = 0 is used, the linear chain's convention for its first tag.  With
+ *     alpha_i(t) = log of the summed potential of all labelled splits of 0..i whose last
+ *                  segment has tag t,
+ *     alpha_i(t) = logsumexp over k = 0..min(K-1, i) and s of  alpha_{i-k-1}(s) + phi[i][k][s][t],
+ *     alpha_{-1}(s) = 0 for s = 0 and -inf otherwise,
+ * logZ = logsumexp_t alpha_{L-1}(t).  Entries with k > i, and rows s > 0 of the first segments,
+ * are never read.  K = 1 is the linear chain.  Empty sequence: logZ = 0.
+ */
+int lccrf_oracle_semi_markov_log_partition(const void *phi, int dtype, const int32_t *lengths,
+                                           int B, int N, int K, int T, double *logZ)
+{
+    if (!phi || !logZ || B < 1 || N < 1 || K < 1 || T < 1 || (dtype != 0 && dtype != 1)) return -1;
+    int err = 0;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int b = 0; b < B; ++b) {
+        int L = clamp_len(lengths, b, N);
+        if (L == 0) { logZ[b] = 0.0; continue; }
+        size_t base = (size_t)b * N * K * T * T;
+        double *alpha = (double *)malloc(sizeof(double) * (size_t)L * T);
+        double *terms = (double *)malloc(sizeof(double) * (size_t)K * T);
+        if (!alpha || !terms) { err = 1; free(alpha); free(terms); continue; }
+        for (int i = 0; i < L; ++i)
+            for (int t = 0; t < T; ++t) {
+                int n = 0;
+                for (int k = 0; k < K && k <= i; ++k) {
+                    size_t m = base + (((size_t)i * K + k) * T) * T;
+                    if (k == i) {               /* first segment: the empty prefix, row 0 */
+                        terms[n++] = phi_at(phi, dtype, m + (size_t)t);
+                    } else {
+                        const double *prev = alpha + (size_t)(i - k - 1) * T;
+                        for (int s2 = 0; s2 < T; ++s2)
+                            terms[n++] = prev[s2] + phi_at(phi, dtype, m + (size_t)s2 * T + t);
+                    }
+                }
+                alpha[(size_t)i * T + t] = logsumexp(terms, n);
+            }
+        logZ[b] = logsumexp(alpha + (size_t)(L - 1) * T, T);
+        free(alpha); free(terms);
+    }
+    return err ? -2 : 0;
+}

@@ -523,3 +523,73 @@ def test_sampling_special_cases(oracle_mod):
     _, best, _ = oracle_mod.viterbi(peaked)
     tags, _ = oracle_mod.sample(peaked, np.full((2, 7), 0.5, dtype=np.float32))
     assert np.array_equal(tags, best)
+
+
+# ---------------------------------------------------------------------------------------
+# semi-Markov CRF (section "Segmentation with Semi-Markov CRF")
+
+def _rand_semi(seed, B, N, K, T, scale=1.0):
+    return (np.random.default_rng(seed).standard_normal((B, N, K, T, T)) * scale).astype(np.float32)
+
+
+def test_semi_markov_against_enumeration(oracle_mod):
+    """Every labelled segmentation enumerated; entries the model never reads (segments that would
+    start before position 0, rows s > 0 of first segments, positions past the length) poisoned."""
+    for seed, (N, K, T) in enumerate([(5, 3, 2), (6, 2, 3), (4, 4, 2), (3, 6, 2), (1, 2, 3)]):
+        phi = _rand_semi(300 + seed, 3, N, K, T, scale=1.5)
+        lens = np.array([N, max(N - 2, 1), 0], dtype=np.int32)
+        want = [brute.semi_markov_log_partition(phi[b].astype(np.float64), int(L)) if L else 0.0
+                for b, L in enumerate(lens)]
+        poisoned = phi.copy()
+        for i in range(N):
+            for k in range(K):
+                if k > i:
+                    poisoned[:, i, k] = np.nan
+                elif k == i:
+                    poisoned[:, i, k, 1:, :] = np.nan
+        for b, L in enumerate(lens):
+            poisoned[b, L:] = np.nan
+        got = oracle_mod.semi_markov_log_partition(poisoned, lens)
+        assert np.allclose(got, want, atol=1e-10), (N, K, T)
+
+
+def test_semi_markov_with_unit_segments_is_the_linear_chain(oracle_mod):
+    """K = 1, or longer segments forbidden: the linear-chain CRF on the k = 0 matrices."""
+    phi = _rand_semi(310, 4, 9, 3, 4, scale=2.0)
+    lens = np.array([9, 5, 1, 0], dtype=np.int32)
+    chain = oracle_mod.log_partition(np.ascontiguousarray(phi[:, :, 0]), lens)
+    assert np.allclose(oracle_mod.semi_markov_log_partition(np.ascontiguousarray(phi[:, :, :1]), lens), chain, atol=1e-12)
+    only_units = phi.copy()
+    only_units[:, :, 1:] = -np.inf
+    assert np.allclose(oracle_mod.semi_markov_log_partition(only_units, lens), chain, atol=1e-12)
+
+
+def test_semi_markov_counts_segmentations(oracle_mod):
+    """Zero potentials: Z counts the labelled segmentations, c(n) = T * sum_{k <= K} c(n - k), c(0) = 1;
+    with K >= L every split is allowed and Z = T (1 + T)^(L - 1)."""
+    N, K, T = 12, 3, 3
+    lens = np.array([12, 7, 3, 1], dtype=np.int32)
+    got = oracle_mod.semi_markov_log_partition(np.zeros((4, N, K, T, T), dtype=np.float32), lens)
+    c = [1]
+    for n in range(1, N + 1):
+        c.append(T * sum(c[n - k] for k in range(1, K + 1) if n - k >= 0))
+    assert np.allclose(np.exp(got), [c[L] for L in lens], rtol=1e-12)
+    got = oracle_mod.semi_markov_log_partition(np.zeros((4, N, N, T, T), dtype=np.float32), lens)
+    assert np.allclose(np.exp(got), [T * (1 + T) ** (L - 1) for L in lens], rtol=1e-12)
+
+
+def test_semi_markov_forbidden_segments_and_bf16(oracle_mod):
+    phi = _rand_semi(320, 2, 6, 3, 2)
+    phi[0, :, :, :, 1] = -np.inf            # tag 1 never used: one tag, scores add up along each split
+    phi[1, 3] = -np.inf                     # no segment may end at position 3 ...
+    phi[1, 4:, 0] = -np.inf                 # ... a unit segment cannot follow it at 4 or 5 either
+    lens = np.array([6, 6], dtype=np.int32)
+    want = [brute.semi_markov_log_partition(phi[b].astype(np.float64), 6) for b in range(2)]
+    assert np.allclose(oracle_mod.semi_markov_log_partition(phi, lens), want, atol=1e-10)
+    dead = phi.copy()
+    dead[1, 5] = -np.inf                    # nothing may end at the last position
+    assert oracle_mod.semi_markov_log_partition(dead, lens)[1] == -np.inf
+    import torch
+    t = torch.from_numpy(_rand_semi(321, 2, 5, 2, 3)).to(torch.bfloat16)
+    want = [brute.semi_markov_log_partition(t[b].double().numpy(), 5) for b in range(2)]
+    assert np.allclose(oracle_mod.semi_markov_log_partition(t), want, atol=1e-10)
