@@ -215,6 +215,23 @@ int lccrf_sample(const void* phi, lccrf_dtype dt, const int32_t* lengths, const 
                  void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * Semi-Markov CRF, log-partition (paper, section "Segmentation with Semi-Markov CRF": the linear
+ * chain's parametrisation with transition matrices, except that a transition may jump over
+ * several positions; forward algorithm in O(K T^2 N)).  A structure splits positions 0..L-1 into
+ * consecutive segments of 1..K positions, each carrying a tag.
+ *   phi     [B][N][K][T][T] (device, dt, 16-byte aligned): phi[b][i][k][s][t] is the log-potential of
+ *           a segment tagged t that ENDS at position i and covers k + 1 positions, after a
+ *           segment tagged s; the first segment (k == i) reads row s = 0 only, the linear
+ *           chain's convention for its first tag.  Entries with k > i, rows s > 0 of first
+ *           segments and positions past the length are never used.  K = 1 is the linear chain.
+ *   logZ    [B] float32 (device).  Empty sequence: 0.  No finite structure: -inf.
+ * Needs no workspace.  Returns LCCRF_ENOTIMPL when the K most recent forward vectors do not fit
+ * one workgroup's local memory (K * T above about 14000); other errors as lccrf_log_partition.
+ */
+int lccrf_semi_markov_log_partition(const void* phi, lccrf_dtype dt, const int32_t* lengths,
+                                    int B, int N, int K, int T, float* logZ, void* stream);
+
+/*
  * The three queries from STRUCTURED potentials: phi[b][i][s][t] = trans[s][t] + emit[b][i][t], the
  * usual tagging parameterisation (per-position emission scores plus one shared transition matrix;
  * the paper's linear-chain CRF takes the dense per-position matrices these stand for, section

@@ -31,7 +31,7 @@ EXPORTS = (
     "lccrf_workspace_bytes", "lccrf_log_partition", "lccrf_marginals", "lccrf_argmax",
     "lccrf_log_partition_algo", "lccrf_marginals_algo", "lccrf_argmax_algo",
     "lccrf_marginals_timed", "lccrf_log_prob", "lccrf_entropy", "lccrf_cross_entropy", "lccrf_kl_divergence",
-    "lccrf_sample", "lccrf_log_partition_structured",
+    "lccrf_sample", "lccrf_semi_markov_log_partition", "lccrf_log_partition_structured",
     "lccrf_marginals_structured", "lccrf_argmax_structured", "lccrf_set_scan_chunk", "lccrf_strerror",
     "lccrf_version",
 )
@@ -77,6 +77,8 @@ def load_library() -> ctypes.CDLL:
     for n in ("lccrf_cross_entropy", "lccrf_kl_divergence"):
         getattr(lib, n).argtypes = [vp, vp, i, vp, i, i, i, vp, vp, sz, vp]
         getattr(lib, n).restype = i
+    lib.lccrf_semi_markov_log_partition.argtypes = [vp, i, vp, i, i, i, i, vp, vp]
+    lib.lccrf_semi_markov_log_partition.restype = i
     lib.lccrf_sample.argtypes = [vp, i, vp, vp, i, i, i, vp, vp, sz, vp]
     lib.lccrf_sample.restype = i
     sbase = [vp, vp, vp, i, i, i]
@@ -279,6 +281,25 @@ def lccrf_sample(phi: torch.Tensor, uniforms: torch.Tensor, lengths: Optional[to
         rc = lib.lccrf_sample(phi.data_ptr(), dt, _len_ptr(lengths, B, phi.device), uniforms.data_ptr(), B, N, T,
                               out.data_ptr(), ws.data_ptr(), nws, _stream(phi.device))
     _check(rc, "lccrf_sample")
+    return out
+
+
+def lccrf_semi_markov_log_partition(phi: torch.Tensor, lengths: Optional[torch.Tensor] = None, *,
+                                    out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """logZ [B] float32 of the semi-Markov CRF with potentials phi [B, N, K, T, T] (float32 or bfloat16, on the
+    GPU, contiguous): phi[b, i, k, s, t] scores a segment tagged t that ends at position i and covers k + 1
+    positions, after a segment tagged s (row 0 for the first segment)."""
+    lib = load_library()
+    if phi.dim() != 5 or phi.shape[3] != phi.shape[4]:
+        raise ValueError(f"phi must be [B, N, K, T, T], got {tuple(phi.shape)}")
+    B, N, K, T, _ = (int(v) for v in phi.shape)
+    dt, _, _, _ = _phi_args(phi.view(B, N * K, T, T))
+    if out is None:
+        out = torch.empty(B, dtype=torch.float32, device=phi.device)
+    with torch.cuda.device(phi.device):
+        rc = lib.lccrf_semi_markov_log_partition(phi.data_ptr(), dt, _len_ptr(lengths, B, phi.device), B, N, K, T,
+                                                 out.data_ptr(), _stream(phi.device))
+    _check(rc, "lccrf_semi_markov_log_partition")
     return out
 
 

@@ -293,6 +293,17 @@ int lccrf_kl_divergence(const void* phi_p, const void* phi_q, lccrf_dtype dt, co
     return cross_query(true, phi_p, phi_q, dt, lengths, B, N, T, out, workspace, workspace_bytes, stream);
 }
 
+int lccrf_semi_markov_log_partition(const void* phi, lccrf_dtype dt, const int32_t* lengths, int B, int N, int K, int T,
+                                    float* logZ, void* stream) {
+    if (!shape_ok(B, N, T) || !dtype_ok(dt) || K < 1) return LCCRF_EINVAL;
+    if ((double)B * N * K * T * T >= 4.0e18) return LCCRF_EINVAL;
+    if (!phi || !logZ) return LCCRF_ENULL;
+    if (!aligned_to(phi, 16) || !aligned_to(logZ, 4) || (lengths && !aligned_to(lengths, 4))) return LCCRF_EALIGN;
+    if (!lccrf::semi_markov_supported(K, T)) return LCCRF_ENOTIMPL;
+    const hipError_t e = lccrf::launch_semi_markov_forward(dt, phi, lengths, B, N, K, T, logZ, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? LCCRF_OK : LCCRF_ELAUNCH;
+}
+
 int lccrf_sample(const void* phi, lccrf_dtype dt, const int32_t* lengths, const float* uniforms, int B, int N, int T,
                  int32_t* tags, void* workspace, size_t workspace_bytes, void* stream) {
     const size_t need = lccrf_workspace_bytes(LCCRF_OP_SAMPLE, B, N, T, dt);
@@ -387,6 +398,6 @@ int lccrf_set_scan_chunk(int chunk) {
     return LCCRF_OK;
 }
 
-int lccrf_version(void) { return 105; }
+int lccrf_version(void) { return 106; }
 
 }  // extern "C"

@@ -83,4 +83,9 @@ hipError_t launch_cross(bool kl, int dtype, const void* phi_p, const void* phi_q
                         int T, float* ua, float* ub, double* Oa, double* Ob, float* ha, float* hb, double* hoff,
                         const double* logZq, float* out, hipStream_t st);
 
+// Semi-Markov CRF forward (lccrf_semi.hip): logZ [B] from phi [B][N][K][T][T].
+bool semi_markov_supported(int K, int T);
+hipError_t launch_semi_markov_forward(int dtype, const void* phi, const int32_t* lengths, int B, int N, int K, int T,
+                                      float* logZ, hipStream_t st);
+
 }  // namespace lccrf

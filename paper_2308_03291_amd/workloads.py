@@ -142,3 +142,18 @@ def random_case(seed: int, B: int, N: int, T: int, *, scale: float = 1.0, ragged
     if dtype == "bf16":
         phi = phi.to(torch.bfloat16)
     return phi.contiguous(), lens
+
+
+def semi_markov_case(seed: int, B: int, N: int, K: int, T: int, *, scale: float = 1.0, ragged: bool = False,
+                     min_len: int = 0, dtype: str = "f32"):
+    """Seeded potentials of a semi-Markov CRF: ``(phi [B,N,K,T,T], lengths int32 [B])``, iid normal
+    times ``scale`` (the paper's benchmark for this model is b=1, n=64, 32 tags, segments up to 8)."""
+    g = _gen(SEED0 * 11 + seed)
+    phi = torch.randn(B, N, K, T, T, generator=g, dtype=torch.float32) * scale
+    if ragged:
+        lens = torch.randint(min_len, N + 1, (B,), generator=g, dtype=torch.int64).to(torch.int32)
+    else:
+        lens = torch.full((B,), N, dtype=torch.int32)
+    if dtype == "bf16":
+        phi = phi.to(torch.bfloat16)
+    return phi.contiguous(), lens

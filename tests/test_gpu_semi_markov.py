@@ -1,0 +1,114 @@
+"""GPU parity of lccrf_semi_markov_log_partition against the CPU oracle (fp64 forward recursion over
+segments, itself pinned against enumeration of labelled segmentations), to the bar of logZ:
+relative 1e-5 (absolute 1e-5 below magnitude 1)."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+from paper_2308_03291_amd import workloads
+from test_gpu_parity import crf  # noqa: F401  (fixture)
+
+pytestmark = pytest.mark.gpu
+
+
+def _check(crf, oracle_mod, phi, lens, what):
+    got = crf.lccrf_semi_markov_log_partition(phi.cuda(), None if lens is None else lens.cuda()).cpu().numpy().astype(np.float64)
+    want = oracle_mod.semi_markov_log_partition(phi, None if lens is None else lens.numpy())
+    same_inf = np.isinf(want) & (got == want)
+    bad = ~same_inf & ~(np.abs(got - want) <= 1e-5 * np.maximum(1.0, np.abs(want)))
+    assert not bad.any(), f"{what}: logZ mismatch at {np.nonzero(bad)[0][:6]}: {got[bad][:4]} vs {want[bad][:4]}"
+
+
+# (T, K, N): tag counts on both sides of every geometry, one and many batches of rows per position,
+# K = 1, K > N, row counts that leave ragged last batches
+SHAPES = [(1, 1, 5), (1, 4, 9), (2, 3, 7), (3, 2, 1), (5, 3, 12), (7, 9, 20), (16, 8, 33), (16, 40, 45), (17, 2, 9),
+          (20, 5, 30), (32, 8, 64), (32, 1, 20), (33, 3, 10), (48, 6, 25), (64, 4, 18), (65, 2, 7), (100, 3, 9),
+          (128, 2, 12), (128, 9, 11), (130, 2, 5), (200, 3, 6), (256, 2, 5), (4, 300, 310)]
+
+
+@pytest.mark.parametrize("T,K,N", SHAPES)
+def test_semi_markov_sweep(crf, oracle_mod, T, K, N):
+    phi, lens = workloads.semi_markov_case(8000 + 131 * T + 7 * K + N, 5, N, K, T, scale=1.5, ragged=True, min_len=0)
+    lens[0] = N
+    lens[1] = min(1, N)
+    # poison what the model never reads: positions past the length, segments that would start before
+    # position 0, rows s > 0 of first segments
+    nan = float("nan")
+    for b in range(5):
+        phi[b, int(lens[b]):] = nan
+    for i in range(min(N, K)):
+        phi[:, i, i + 1:] = nan
+        phi[:, i, i, 1:, :] = nan
+    _check(crf, oracle_mod, phi, lens, f"T={T} K={K} N={N}")
+
+
+@pytest.mark.parametrize("T", [5, 32, 96])
+def test_unit_segments_are_the_linear_chain(crf, T):
+    """K = 1, and longer segments forbidden: the library's own linear-chain logZ on the k = 0 matrices."""
+    phi, lens = workloads.semi_markov_case(8100 + T, 4, 40, 3, T, scale=2.0, ragged=True, min_len=1)
+    chain = crf.lccrf_log_partition(phi[:, :, 0].contiguous().cuda(), lens.cuda()).cpu()
+    got = crf.lccrf_semi_markov_log_partition(phi[:, :, :1].contiguous().cuda(), lens.cuda()).cpu()
+    assert torch.allclose(got, chain, rtol=2e-6, atol=1e-5)
+    phi[:, :, 1:] = float("-inf")
+    got = crf.lccrf_semi_markov_log_partition(phi.cuda(), lens.cuda()).cpu()
+    assert torch.allclose(got, chain, rtol=2e-6, atol=1e-5)
+
+
+def test_zero_potentials_count_the_segmentations(crf):
+    """Z = number of labelled segmentations: c(n) = T sum_{k <= K} c(n - k); T (1 + T)^(L - 1) when K >= L."""
+    N, K, T = 40, 3, 4
+    lens = torch.tensor([40, 17, 3, 1, 0], dtype=torch.int32)
+    got = crf.lccrf_semi_markov_log_partition(torch.zeros(5, N, K, T, T, device="cuda"), lens.cuda()).cpu().numpy()
+    c = [1]
+    for n in range(1, N + 1):
+        c.append(T * sum(c[n - k] for k in range(1, K + 1) if n - k >= 0))
+    want = np.array([math.log(c[int(L)]) for L in lens])
+    assert np.allclose(got, want, rtol=1e-5, atol=1e-6)
+    got = crf.lccrf_semi_markov_log_partition(torch.zeros(5, N, N, T, T, device="cuda"), lens.cuda()).cpu().numpy()
+    want = np.array([math.log(T) + (int(L) - 1) * math.log(1 + T) if L else 0.0 for L in lens])
+    assert np.allclose(got, want, rtol=1e-5, atol=1e-6)
+
+
+@pytest.mark.parametrize("T,K", [(16, 4), (48, 3)])
+def test_semi_markov_bf16_peaked_offsets_and_forbidden_segments(crf, oracle_mod, T, K):
+    phi, lens = workloads.semi_markov_case(8200 + T, 4, 50, K, T, scale=6.0, ragged=True, min_len=20, dtype="bf16")
+    _check(crf, oracle_mod, phi, lens, f"peaked bf16 T={T}")
+    phi, lens = workloads.semi_markov_case(8300 + T, 3, 60, K, T, scale=1.0)
+    _check(crf, oracle_mod, (phi + 40.0).contiguous(), lens, f"offset T={T}")
+    _check(crf, oracle_mod, (phi - 300.0).contiguous(), lens, f"negative offset T={T}")
+    phi, _ = workloads.semi_markov_case(8400 + T, 5, 30, K, T)
+    ninf = float("-inf")
+    phi[0, :, :, :, 3] = ninf              # tag 3 never used
+    phi[1, 10] = ninf                      # nothing ends at position 10: a segment must jump over it
+    phi[2, :, 1:] = ninf                   # unit segments only ...
+    phi[2, 5, 0] = ninf                    # ... and none may end at position 5: no structure at all
+    mask = torch.rand(30, K, T, T, generator=torch.Generator().manual_seed(7)) < 0.7
+    phi[3][mask] = ninf
+    phi[3, :, 0, torch.arange(T), torch.arange(T)] = 0.0
+    phi[4, 29] = ninf                      # nothing may end at the last position
+    _check(crf, oracle_mod, phi, None, f"-inf T={T}")
+    got = crf.lccrf_semi_markov_log_partition(phi.cuda()).cpu().numpy()
+    assert got[4] == -np.inf and got[2] == -np.inf
+
+
+def test_paper_benchmark_shape_and_a_long_batch(crf, oracle_mod):
+    """The paper's benchmark size for this model (b=1, n=64, 32 tags, segments up to 8), and a batch
+    of longer sequences."""
+    phi, lens = workloads.semi_markov_case(8500, 1, 64, 8, 32)
+    _check(crf, oracle_mod, phi, lens, "paper shape")
+    phi, lens = workloads.semi_markov_case(8501, 6, 700, 8, 32, scale=2.0, ragged=True, min_len=300)
+    _check(crf, oracle_mod, phi, lens, "long batch")
+    phi, lens = workloads.semi_markov_case(8502, 2, 3000, 4, 16, scale=3.0, dtype="bf16")
+    _check(crf, oracle_mod, phi, lens, "long bf16")
+
+
+def test_semi_markov_argument_checks(crf):
+    with pytest.raises(ValueError, match="B, N, K, T, T"):
+        crf.lccrf_semi_markov_log_partition(torch.zeros(2, 4, 3, 3, device="cuda"))
+    with pytest.raises(crf.LccrfError, match="not available"):
+        crf.lccrf_semi_markov_log_partition(torch.zeros(1, 2, 200, 128, 128, device="cuda"))   # 200 vectors of 128 floats
+    out = crf.lccrf_semi_markov_log_partition(torch.zeros(2, 4, 2, 3, 3, device="cuda"),
+                                              torch.tensor([0, 1], dtype=torch.int32, device="cuda")).cpu().numpy()
+    assert out[0] == 0.0 and out[1] == pytest.approx(math.log(3), rel=1e-6)
