@@ -15,7 +15,7 @@ Extra objects in the line:
   cpu_baseline  the CPU oracle (as it stands, OpenMP over the batch) timed on this host on a
                 bounded sample of the same workload.
   other_queries log-partition alone, Viterbi decode, entropy, the log-probability of a path, one sample, and the
-                cross-entropy and KL divergence against a second chain,
+                cross-entropy and KL divergence against a second chain, the semi-Markov log-partition over the same bytes,
                 timed the same way (context).
 """
 from __future__ import annotations
@@ -203,7 +203,13 @@ def main():
                 ("log_prob", lambda: crf.lccrf_log_prob(phi, path, lens, out=score, workspace=ws), esz),
                 ("sample", lambda: crf.lccrf_sample(phi, uniforms, lens, out=tags, workspace=ws), esz),
                 ("cross_entropy", lambda: crf.lccrf_cross_entropy(phi, phi_q, lens, out=score, workspace=ws), 3 * esz),
-                ("kl_divergence", lambda: crf.lccrf_kl_divergence(phi, phi_q, lens, out=score, workspace=ws), 3 * esz)):
+                ("kl_divergence", lambda: crf.lccrf_kl_divergence(phi, phi_q, lens, out=score, workspace=ws), 3 * esz),
+                # the same bytes read as a semi-Markov CRF: N / 8 positions, segments of up to 8 positions
+                ("semi_markov_log_partition_k8",
+                 (lambda: crf.lccrf_semi_markov_log_partition(phi.view(w.B, w.N // 8, 8, w.T, w.T), out=score))
+                 if w.N % 8 == 0 else None, esz)):
+            if fn is None:
+                continue
             for _ in range(2):
                 fn()
             evs = new_events(2 * max(5, args.steps // 2))
