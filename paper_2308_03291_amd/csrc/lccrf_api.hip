@@ -15,6 +15,7 @@ int g_scan_chunk = kDefaultScanChunk;
 struct SumWorkspace {
     size_t ua, ub, Oa, Ob, mail, failed;
     size_t Pl, rel, base, Fv, OF, Gv, OG;  // chunked scan (T <= 16 only, else empty)
+    size_t Pl2, rel2, base2, Fv2, OF2, Gv2, OG2;  // its group level (many chunks only, else empty)
     size_t lz64, ha, hb, hoff;             // log-probability, entropy and cross-entropy queries
     size_t total;
 };
@@ -35,6 +36,16 @@ inline SumWorkspace sum_workspace(size_t B, size_t N, size_t T) {
     w.OF = off; off += round_up(BC * sizeof(double));
     w.Gv = off; off += round_up(BC * T * sizeof(float));
     w.OG = off; off += round_up(BC * sizeof(double));
+    const size_t C = (N + g_scan_chunk - 1) / g_scan_chunk;
+    const size_t gs = BC ? (size_t)lccrf::scan_group_size((int)C) : 0;
+    const size_t BG = gs ? B * ((C + gs - 1) / gs) : 0;
+    w.Pl2 = off; off += round_up(BG * 256 * sizeof(float));
+    w.rel2 = off; off += round_up(BG * 16 * sizeof(float));
+    w.base2 = off; off += round_up(BG * sizeof(double));
+    w.Fv2 = off; off += round_up(BG * T * sizeof(float));
+    w.OF2 = off; off += round_up(BG * sizeof(double));
+    w.Gv2 = off; off += round_up(BG * T * sizeof(float));
+    w.OG2 = off; off += round_up(BG * sizeof(double));
     w.lz64 = off; off += round_up(B * sizeof(double));
     w.ha = off; off += round_up(B * T * sizeof(float));
     w.hb = off; off += round_up(B * T * sizeof(float));
@@ -68,6 +79,13 @@ inline bool shape_ok(int B, int N, int T) {
 }
 inline bool dtype_ok(int dt) { return dt == LCCRF_F32 || dt == LCCRF_BF16; }
 inline bool aligned_to(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
+
+lccrf::ScanGroupBuffers group_buffers(const SumWorkspace& w, char* base) {
+    return {reinterpret_cast<float*>(base + w.Pl2), reinterpret_cast<float*>(base + w.rel2),
+            reinterpret_cast<double*>(base + w.base2), reinterpret_cast<float*>(base + w.Fv2),
+            reinterpret_cast<double*>(base + w.OF2), reinterpret_cast<float*>(base + w.Gv2),
+            reinterpret_cast<double*>(base + w.OG2)};
+}
 
 int check_common(const void* phi, int dt, int B, int N, int T, const void* ws, size_t ws_bytes, size_t need,
                  int algo) {
@@ -109,8 +127,8 @@ int sum_query(int op, const void* phi, int dt, const int32_t* lengths, int B, in
         hipError_t e = lccrf::launch_scan_boundaries(dt, phi, lengths, B, N, T, g_scan_chunk,
                                                      reinterpret_cast<float*>(base + w.Pl),
                                                      reinterpret_cast<float*>(base + w.rel),
-                                                     reinterpret_cast<double*>(base + w.base), Fv, OF, Gv, OG, logZ,
-                                                     op == 1, st);
+                                                     reinterpret_cast<double*>(base + w.base), Fv, OF, Gv, OG,
+                                                     group_buffers(w, base), logZ, op == 1, st);
         if (e == hipSuccess && op == 1)
             e = lccrf::launch_chunked_marginals(dt, phi, lengths, B, N, T, reinterpret_cast<float*>(base + w.ua),
                                                 reinterpret_cast<float*>(base + w.ub),
@@ -222,7 +240,8 @@ static hipError_t launch_log_partition64(const void* phi, int dt, const int32_t*
             dt, phi, lengths, B, N, T, g_scan_chunk, reinterpret_cast<float*>(base + w.Pl),
             reinterpret_cast<float*>(base + w.rel), reinterpret_cast<double*>(base + w.base),
             reinterpret_cast<float*>(base + w.Fv), reinterpret_cast<double*>(base + w.OF),
-            reinterpret_cast<float*>(base + w.Gv), reinterpret_cast<double*>(base + w.OG), nullptr, false, st, lz64);
+            reinterpret_cast<float*>(base + w.Gv), reinterpret_cast<double*>(base + w.OG), group_buffers(w, base),
+            nullptr, false, st, lz64);
     return lccrf::launch_sequential_sum(0, dt, phi, lengths, B, N, T, reinterpret_cast<float*>(base + w.ua),
                                         reinterpret_cast<float*>(base + w.ub), reinterpret_cast<double*>(base + w.Oa),
                                         reinterpret_cast<double*>(base + w.Ob), nullptr, nullptr, st, nullptr, false,

@@ -39,10 +39,23 @@ hipError_t launch_pair_marginals(int dtype, const void* phi, const int32_t* leng
 // positions (C = ceil(N / chunk) chunks per sequence), the chunk's transfer matrix (Pl: 256 floats, rel: 16
 // floats, base: 1 double) and alpha / beta at the chunk's last position (Fv, Gv: T floats; OF, OG: 1
 // double), and logZ if non-null.  with_beta false: forward vectors and logZ only.
+// With many chunks the serial pass over chunks is itself split into groups of scan_group_size(C) chunks
+// (0: not split); the group-level copies of the arrays above ([B][G], G = ceil(C / group size)) live in gb.
 bool scan_supported(int T);
+int scan_group_size(int C);
+struct ScanGroupBuffers {
+    float* Pl2;
+    float* rel2;
+    double* base2;
+    float* Fv2;
+    double* OF2;
+    float* Gv2;
+    double* OG2;
+};
 hipError_t launch_scan_boundaries(int dtype, const void* phi, const int32_t* lengths, int B, int N, int T, int chunk,
                                   float* Pl, float* rel, double* base, float* Fv, double* OF, float* Gv, double* OG,
-                                  float* logZ, bool with_beta, hipStream_t st, double* logZ64 = nullptr);
+                                  const ScanGroupBuffers& gb, float* logZ, bool with_beta, hipStream_t st,
+                                  double* logZ64 = nullptr);
 
 // log p(y) = score(y) - logZ for one tag path per sequence (lccrf_extras.hip); logZ64: [B] doubles
 // already computed on the same stream.

@@ -10,7 +10,11 @@
 //       P_c[r][s] = log sum over paths that enter the chunk from tag r and leave it in tag s;
 //   phase B (chunk_boundary_kernel, two waves per sequence, serial over the chunks only):
 //       alpha at the last position of every chunk (F_c = F_{c-1} (x) P_c) and beta at the last
-//       position of every chunk (G_{c-1} = P_c (x) G_c), and logZ from the last F;
+//       position of every chunk (G_{c-1} = P_c (x) G_c), and logZ from the last F.  With many
+//       chunks this is itself run as a scan: group_product_kernel multiplies the products of
+//       every group of chunks (all groups at once, the very code of phase A with chunk products in
+//       the place of potentials), phase B runs over the groups, and then over the chunks of
+//       every group at once from the group's boundary vectors;
 //   phase C (the chain kernels of lccrf_chain.hip, one pair of workgroups per chunk):
 //       the ordinary two-chain forward-backward inside every chunk, started from F and G.
 //
@@ -55,6 +59,19 @@ struct ScanArgs {
     float* logZ;   // [B] or null
     int with_beta;
     double* logZ64;  // [B] or null: the same in double precision
+    // Grouped runs (GS > 0): a unit of work covers GS consecutive chunks, G = ceil(C / GS) groups a
+    // sequence.  group_product_kernel writes the product of every group to (Pl2, rel2, base2), laid
+    // out like (Pl, rel, base) with G in the place of C; chunk_boundary_kernel starts every group
+    // from the boundary vectors of the groups (Fin .. OGin, [B][G] like Fv .. OG) instead of walking
+    // the whole sequence.
+    int GS, G;
+    float* Pl2;
+    float* rel2;
+    double* base2;
+    const float* Fin;
+    const double* OFin;
+    const float* Gin;
+    const double* OGin;
 };
 
 // First and last position whose matrix belongs to chunk c (first > last: none).
@@ -66,23 +83,79 @@ __device__ __forceinline__ void chunk_range(int c, int chunk, int L, int& first,
 
 // ---------------------------------------------------------------------------------------
 // Phase A.
+//
+// Where the matrices of a product come from.  Lane (g = lane / 16, j = lane % 16) handles the
+// entries M_i[g + 4v][j], v = 0..3, of matrix i (row: tag before, column: tag after), in base-2
+// logarithms, -inf outside T x T; every matrix may carry a common offset besides.
 template <typename TIN>
-__global__ __launch_bounds__(64) void chunk_product_kernel(ScanArgs a) {
-    __shared__ float Pc[16][17];
-    __shared__ float Ph[16][17];
-    const int lane = threadIdx.x;
-    const int b = blockIdx.x / a.C, c = blockIdx.x % a.C;
-    const int T = a.T, N = a.N;
-    const int L = clamp_length(a.lengths, b, N);
-    if (c * a.chunk >= L) return;
-    int first, last;
-    chunk_range(c, a.chunk, L, first, last);
-    const size_t TT = (size_t)T * T;
-    const TIN* phib = static_cast<const TIN*>(a.phi) + (size_t)b * N * TT;
-    float* Pout = a.Pl + ((size_t)b * a.C + c) * 256;
-    float* rel_out = a.rel + ((size_t)b * a.C + c) * 16;
-    double* base_out = a.base + (size_t)b * a.C + c;
+struct PotentialMatrices {  // the potentials phi_i of one sequence
+    static constexpr int PF = kScanPF;
+    struct Slot { float x[4]; };
+    const TIN* phib;
+    int T;
+    size_t TT;
+    int off[4];
+    bool in[4];
+    __device__ PotentialMatrices(const TIN* p, int T_, int lane) : phib(p), T(T_), TT((size_t)T_ * T_) {
+        const int g = lane >> 4, j = lane & 15;
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+            const int s = g + 4 * v;
+            in[v] = s < T && j < T;
+            off[v] = (s < T ? s : T - 1) * T + (j < T ? j : T - 1);
+        }
+    }
+    __device__ __forceinline__ void load(int i, Slot& sl) const {
+        const TIN* m = phib + (size_t)i * TT;
+#pragma unroll
+        for (int v = 0; v < 4; ++v) sl.x[v] = Elem<TIN>::get(m + off[v]);
+    }
+    __device__ __forceinline__ double entries(const Slot& sl, float (&x)[4]) const {
+#pragma unroll
+        for (int v = 0; v < 4; ++v) x[v] = in[v] ? sl.x[v] * kLog2e : LCCRF_NEG_INF;
+        return 0.0;
+    }
+    __device__ __forceinline__ float entry(int i, int r, int t) const {  // one entry, straight from memory
+        return (r < T && t < T) ? Elem<TIN>::get(phib + (size_t)i * TT + r * T + t) * kLog2e : LCCRF_NEG_INF;
+    }
+    __device__ __forceinline__ double offset(int) const { return 0.0; }
+};
 
+struct ChunkMatrices {  // the chunk products of one sequence, as phase A has written them
+    static constexpr int PF = 4;
+    struct Slot { float p[4], r[4]; double b; };
+    const float* Pl;
+    const float* rel;
+    const double* base;
+    int T, g, j;
+    __device__ ChunkMatrices(const float* Pl_, const float* rel_, const double* base_, int T_, int lane)
+        : Pl(Pl_), rel(rel_), base(base_), T(T_), g(lane >> 4), j(lane & 15) {}
+    __device__ __forceinline__ void load(int c, Slot& sl) const {
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+            sl.p[v] = Pl[(size_t)c * 256 + j * 16 + g + 4 * v];
+            sl.r[v] = rel[(size_t)c * 16 + g + 4 * v];
+        }
+        sl.b = base[c];
+    }
+    __device__ __forceinline__ double entries(const Slot& sl, float (&x)[4]) const {
+#pragma unroll
+        for (int v = 0; v < 4; ++v) x[v] = (g + 4 * v < T && j < T) ? sl.p[v] + sl.r[v] : LCCRF_NEG_INF;
+        return sl.b;
+    }
+    __device__ __forceinline__ float entry(int c, int r, int t) const {
+        return (r < T && t < T) ? Pl[(size_t)c * 256 + t * 16 + r] + rel[(size_t)c * 16 + r] : LCCRF_NEG_INF;
+    }
+    __device__ __forceinline__ double offset(int c) const { return base[c]; }
+};
+
+// Product of matrices first .. last of `src` (none: the identity), by one wave, written as
+// log2 P[r][s] = Pout[s * 16 + r] + rel_out[r] + *base_out.
+template <typename Src>
+__device__ __forceinline__ void matrix_product(const Src& src, int first, int last, int T, float* __restrict__ Pout,
+                                               float* __restrict__ rel_out, double* __restrict__ base_out,
+                                               float (*Pc)[17], float (*Ph)[17]) {
+    const int lane = threadIdx.x;
     // ---- linear-domain product on the matrix cores, in double precision for its exponent range.
     // D[s][r] (exit tag s, entry tag r) sits in the accumulator layout of the 16x16x4 f64 MFMA:
     // lane (g = lane / 16, j = lane % 16) holds D[g + 4v][j], v = 0..3.  The same lane loads
@@ -92,14 +165,9 @@ __global__ __launch_bounds__(64) void chunk_product_kernel(ScanArgs a) {
     // needs no data movement between positions.
     {
         const int g = lane >> 4, j = lane & 15;
-        int off[4];
         bool in[4];
 #pragma unroll
-        for (int v = 0; v < 4; ++v) {
-            const int s = g + 4 * v;
-            in[v] = s < T && j < T;
-            off[v] = (s < T ? s : T - 1) * T + (j < T ? j : T - 1);
-        }
+        for (int v = 0; v < 4; ++v) in[v] = g + 4 * v < T && j < T;
         // The zero pattern of D (1 where some path exists) is carried along by a product of 0/1
         // matrices on the f32 MFMA, from the first matrix with a -inf entry on (until then D is
         // the identity or has no zero).  That instruction numbers its output rows 4g + v, so it
@@ -112,21 +180,16 @@ __global__ __launch_bounds__(64) void chunk_product_kernel(ScanArgs a) {
             D[v] = (g + 4 * v == j) ? 1.0 : 0.0;
             Z[v] = (g + 4 * v == j) ? 1.f : 0.f;
         }
-        float ring[kScanPF][4];
-        auto load = [&](int i, int slot) {
-            const TIN* m = phib + (size_t)i * TT;
-#pragma unroll
-            for (int v = 0; v < 4; ++v) ring[slot][v] = Elem<TIN>::get(m + off[v]);
-        };
+        typename Src::Slot ring[Src::PF];
+        auto load = [&](int i, int slot) { src.load(i, ring[slot]); };
         double Msum = 0.0;
         int esum = 0;
         bool bad = false, tracking = false, started = false;
-        walk<kScanPF>(first, last, +1, load, [&](int, int slot) {
+        walk<Src::PF>(first, last, +1, load, [&](int, int slot) {
             float x[4];
-#pragma unroll
-            for (int v = 0; v < 4; ++v) x[v] = in[v] ? ring[slot][v] * kLog2e : LCCRF_NEG_INF;
+            const double common = src.entries(ring[slot], x);
             const float m = finite_or_zero(xor_max<1, 64>(fmaxf(fmaxf(x[0], x[1]), fmaxf(x[2], x[3]))));
-            Msum += (double)m;
+            Msum += (double)m + common;
             int nz = 0;
             f64x4 acc = {0.0, 0.0, 0.0, 0.0};
 #pragma unroll
@@ -202,13 +265,15 @@ __global__ __launch_bounds__(64) void chunk_product_kernel(ScanArgs a) {
 #pragma unroll
         for (int jj = 0; jj < 4; ++jj) out[jj] = (r == 4 * q + jj) ? 0.f : LCCRF_NEG_INF;
         float sg = 0.f;  // integer valued
+        double osum = 0.0;
         for (int i = first; i <= last; ++i) {
+            osum += src.offset(i);
             __syncthreads();
 #pragma unroll
             for (int jj = 0; jj < 4; ++jj) {
                 const int t = 4 * q + jj;
                 Pc[r][t] = out[jj];
-                Ph[r][t] = (r < T && t < T) ? Elem<TIN>::get(phib + (size_t)i * TT + r * T + t) * kLog2e : LCCRF_NEG_INF;
+                Ph[r][t] = src.entry(i, r, t);
             }
             __syncthreads();
             float mx[4] = {LCCRF_NEG_INF, LCCRF_NEG_INF, LCCRF_NEG_INF, LCCRF_NEG_INF};
@@ -240,36 +305,84 @@ __global__ __launch_bounds__(64) void chunk_product_kernel(ScanArgs a) {
             Pout[t * 16 + r] = (r < T && t < T) ? out[jj] : LCCRF_NEG_INF;
         }
         if (q == 0) rel_out[r] = ef - emax;
-        if (lane == 0) *base_out = (double)emax;
+        if (lane == 0) *base_out = osum + (double)emax;
     }
 }
 
+// One wave per chunk: the product of the chunk's potentials.
+template <typename TIN>
+__global__ __launch_bounds__(64) void chunk_product_kernel(ScanArgs a) {
+    __shared__ float Pc[16][17];
+    __shared__ float Ph[16][17];
+    const int b = blockIdx.x / a.C, c = blockIdx.x % a.C;
+    const int T = a.T, N = a.N;
+    const int L = clamp_length(a.lengths, b, N);
+    if (c * a.chunk >= L) return;
+    int first, last;
+    chunk_range(c, a.chunk, L, first, last);
+    const PotentialMatrices<TIN> src(static_cast<const TIN*>(a.phi) + (size_t)b * N * T * T, T, threadIdx.x);
+    const size_t bc = (size_t)b * a.C + c;
+    matrix_product(src, first, last, T, a.Pl + bc * 256, a.rel + bc * 16, a.base + bc, Pc, Ph);
+}
+
+// One wave per group of GS chunks: the product of the group's chunk products.
+__global__ __launch_bounds__(64) void group_product_kernel(ScanArgs a) {
+    __shared__ float Pc[16][17];
+    __shared__ float Ph[16][17];
+    const int b = blockIdx.x / a.G, g = blockIdx.x % a.G;
+    const int L = clamp_length(a.lengths, b, a.N);
+    const int Cb = (L + a.chunk - 1) / a.chunk;  // chunks of this sequence
+    const int c0 = g * a.GS;
+    if (c0 >= Cb) return;
+    const int c1 = (c0 + a.GS < Cb ? c0 + a.GS : Cb) - 1;
+    const size_t cb = (size_t)b * a.C, bg = (size_t)b * a.G + g;
+    const ChunkMatrices src(a.Pl + cb * 256, a.rel + cb * 16, a.base + cb, a.T, threadIdx.x);
+    matrix_product(src, c0, c1, a.T, a.Pl2 + bg * 256, a.rel2 + bg * 16, a.base2 + bg, Pc, Ph);
+}
+
 // ---------------------------------------------------------------------------------------
-// Phase B.  Workgroup 2b runs the forward vector of sequence b through its chunk products,
-// workgroup 2b + 1 the backward vector.  Lane (o = lane / 4, q = lane % 4) produces output
-// entry o from the four input entries 4q .. 4q+3; the vector is passed from one step to the
-// next through LDS.
+// Phase B.  One wave runs the forward vector through a run of chunk products, another the
+// backward vector: the whole sequence (GS = 0: waves 2b and 2b + 1), or the chunks of one group
+// (GS > 0: waves 2 (b G + g) and 2 (b G + g) + 1), started from the boundary vectors of the
+// groups.  Lane (o = lane / 4, q = lane % 4) produces output entry o from the four input entries
+// 4q .. 4q+3; the vector travels from step to step in registers: entry t of the new vector sits in
+// lanes 4t .. 4t+3, lane (o, q) fetches entries 4q .. 4q+3 with four lane reads.  It is normalised
+// by the maximum of the PREVIOUS vector (one step stale: consecutive maxima differ little), so
+// the wave-wide maximum is off the chain of dependent instructions.
 template <typename TIN>
 __global__ __launch_bounds__(64) void chunk_boundary_kernel(ScanArgs a) {
     const int lane = threadIdx.x, o = lane >> 2, q = lane & 3;
-    const int b = blockIdx.x >> 1, dir = blockIdx.x & 1;
+    const int dir = blockIdx.x & 1;
+    const int unit = blockIdx.x >> 1;
+    const bool grouped = a.GS > 0;
+    const int b = grouped ? unit / a.G : unit, g = grouped ? unit % a.G : 0;
     const int T = a.T, N = a.N;
     const int L = clamp_length(a.lengths, b, N);
     if (L == 0) {
-        if (dir == 0 && lane == 0 && a.logZ) a.logZ[b] = 0.f;
-        if (dir == 0 && lane == 0 && a.logZ64) a.logZ64[b] = 0.0;
+        if (!grouped && dir == 0 && lane == 0 && a.logZ) a.logZ[b] = 0.f;
+        if (!grouped && dir == 0 && lane == 0 && a.logZ64) a.logZ64[b] = 0.0;
         return;
     }
     if (dir == 1 && !a.with_beta) return;
     const int Cb = (L + a.chunk - 1) / a.chunk;
-    const size_t cb = (size_t)b * a.C;
+    const int c0 = grouped ? g * a.GS : 0;  // chunks c0 .. c1 are this wave's
+    if (c0 >= Cb) return;
+    const int c1 = (grouped && c0 + a.GS < Cb ? c0 + a.GS : Cb) - 1;
+    const size_t cb = (size_t)b * a.C, bg = (size_t)b * a.G;
     double O = 0.0;
 
     if (dir == 0) {
-        const TIN* phib = static_cast<const TIN*>(a.phi) + (size_t)b * N * T * T;
-        float v = (lane < T) ? Elem<TIN>::get(phib + lane) * kLog2e : LCCRF_NEG_INF;  // alpha_0
-        float d = finite_or_zero(xor_max<1, 64>(v));
-        O = (double)d;
+        float nv;  // alpha before chunk c0, entry o in lanes 4o .. 4o+3
+        if (c0 == 0) {
+            const TIN* phib = static_cast<const TIN*>(a.phi) + (size_t)b * N * T * T;
+            const float v = (lane < T) ? Elem<TIN>::get(phib + lane) * kLog2e : LCCRF_NEG_INF;  // alpha_0
+            const float d = finite_or_zero(xor_max<1, 64>(v));
+            O = (double)d;
+            nv = (o < T) ? __shfl(v, o, 64) - d : LCCRF_NEG_INF;
+        } else {
+            nv = (o < T) ? a.Fin[(bg + g - 1) * T + o] : LCCRF_NEG_INF;
+            O = a.OFin[bg + g - 1];
+        }
         float pm[kScanPF][4], rl[kScanPF][4];
         double bs[kScanPF];
         auto load = [&](int c, int slot) {
@@ -279,13 +392,8 @@ __global__ __launch_bounds__(64) void chunk_boundary_kernel(ScanArgs a) {
             rl[slot][0] = e.x; rl[slot][1] = e.y; rl[slot][2] = e.z; rl[slot][3] = e.w;
             bs[slot] = a.base[cb + c];
         };
-        // The vector travels from step to step in registers: entry t of the new vector sits in lanes
-        // 4t .. 4t+3, lane (o, q) fetches entries 4q .. 4q+3 with four lane reads.  It is normalised by
-        // the maximum of the PREVIOUS vector (one step stale: consecutive maxima differ little), so the
-        // wave-wide maximum is off the chain of dependent instructions.
-        float nv = (o < T) ? __shfl(v, o, 64) - d : LCCRF_NEG_INF;  // alpha_0, entry o in lanes 4o .. 4o+3
         float dprev = 0.f;
-        walk<kScanPF>(0, Cb - 1, +1, load, [&](int c, int slot) {
+        walk<kScanPF>(c0, c1, +1, load, [&](int c, int slot) {
             const float f0 = lane_bperm(nv, 16 * q), f1 = lane_bperm(nv, 16 * q + 4);
             const float f2 = lane_bperm(nv, 16 * q + 8), f3 = lane_bperm(nv, 16 * q + 12);
             const float x0 = f0 + (pm[slot][0] + rl[slot][0]), x1 = f1 + (pm[slot][1] + rl[slot][1]);
@@ -300,7 +408,7 @@ __global__ __launch_bounds__(64) void chunk_boundary_kernel(ScanArgs a) {
             if (q == 0 && o < T) a.Fv[(cb + c) * T + o] = nv;
             if (lane == 0) a.OF[cb + c] = O;
         });
-        if (a.logZ || a.logZ64) {
+        if (!grouped && (a.logZ || a.logZ64)) {
             // entry t sits in lanes 4t .. 4t+3: count it once
             const float S = xor_sum<1, 64>(q == 0 ? ex2(nv - dprev) : 0.f);
             const double lz = (O + (double)dprev + (double)lg2(S)) * kLn2;
@@ -308,7 +416,13 @@ __global__ __launch_bounds__(64) void chunk_boundary_kernel(ScanArgs a) {
             if (lane == 0 && a.logZ64) a.logZ64[b] = lz;
         }
     } else {
-        float nv = (o < T) ? 0.f : LCCRF_NEG_INF;  // beta at the last position, entry o in lanes 4o .. 4o+3
+        float nv;  // beta at the last position of chunk c1, entry o in lanes 4o .. 4o+3
+        if (c1 == Cb - 1) {
+            nv = (o < T) ? 0.f : LCCRF_NEG_INF;
+        } else {
+            nv = (o < T) ? a.Gin[(bg + g) * T + o] : LCCRF_NEG_INF;
+            O = a.OGin[bg + g];
+        }
         float dprev = 0.f;
         float pm[kScanPF][4], rl[kScanPF];
         double bs[kScanPF];
@@ -319,7 +433,8 @@ __global__ __launch_bounds__(64) void chunk_boundary_kernel(ScanArgs a) {
             rl[slot] = a.rel[(cb + c) * 16 + o];
             bs[slot] = a.base[cb + c];
         };
-        walk<kScanPF>(Cb - 1, 1, -1, load, [&](int c, int slot) {
+        // chunk c takes beta at its last position to beta at the last position of chunk c - 1
+        walk<kScanPF>(c1, c0 > 1 ? c0 : 1, -1, load, [&](int c, int slot) {
             const float g0 = lane_bperm(nv, 16 * q), g1 = lane_bperm(nv, 16 * q + 4);
             const float g2 = lane_bperm(nv, 16 * q + 8), g3 = lane_bperm(nv, 16 * q + 12);
             const float x0 = pm[slot][0] + g0, x1 = pm[slot][1] + g1, x2 = pm[slot][2] + g2, x3 = pm[slot][3] + g3;
@@ -499,22 +614,54 @@ __global__ __launch_bounds__(64) void chunk_maxplus_boundary_kernel(MaxScanArgs 
 // ---------------------------------------------------------------------------------------
 bool scan_supported(int T) { return T >= 1 && T <= 16; }
 
-hipError_t launch_scan_boundaries(int dtype, const void* phi, const int32_t* lengths, int B, int N, int T, int chunk,
-                                  float* Pl, float* rel, double* base, float* Fv, double* OF, float* Gv, double* OG,
-                                  float* logZ, bool with_beta, hipStream_t st, double* logZ64) {
-    const int C = (N + chunk - 1) / chunk;
-    ScanArgs a{phi, lengths, B, N, T, chunk, C, Pl, rel, base, Fv, OF, Gv, OG, logZ, with_beta ? 1 : 0, logZ64};
-    if (dtype == 0)
-        hipLaunchKernelGGL(chunk_product_kernel<float>, dim3(B * C), dim3(64), 0, st, a);
-    else
-        hipLaunchKernelGGL(chunk_product_kernel<uint16_t>, dim3(B * C), dim3(64), 0, st, a);
+// Chunks per group when phase B is itself run as a scan; 0: one serial pass over all chunks.  The
+// group products cost about 3.5 times a vector step each and two serial stages follow them
+// (over groups, over the chunks of a group), which puts the best group near sqrt(C) / 2.
+int scan_group_size(int C) {
+    if (C < 64) return 0;
+    int gs = 4;
+    while (gs * gs * 4 < C) gs *= 2;
+    return gs;
+}
+
+template <typename TIN>
+static hipError_t launch_scan_boundaries_t(ScanArgs a, const ScanGroupBuffers& gb, hipStream_t st) {
+    hipLaunchKernelGGL(chunk_product_kernel<TIN>, dim3(a.B * a.C), dim3(64), 0, st, a);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    if (dtype == 0)
-        hipLaunchKernelGGL(chunk_boundary_kernel<float>, dim3(2 * B), dim3(64), 0, st, a);
-    else
-        hipLaunchKernelGGL(chunk_boundary_kernel<uint16_t>, dim3(2 * B), dim3(64), 0, st, a);
+    const int gs = scan_group_size(a.C);
+    if (gs == 0) {
+        hipLaunchKernelGGL(chunk_boundary_kernel<TIN>, dim3(2 * a.B), dim3(64), 0, st, a);
+        return hipGetLastError();
+    }
+    const int G = (a.C + gs - 1) / gs;
+    // products of the groups
+    ScanArgs p = a;
+    p.GS = gs; p.G = G; p.Pl2 = gb.Pl2; p.rel2 = gb.rel2; p.base2 = gb.base2;
+    hipLaunchKernelGGL(group_product_kernel, dim3(a.B * G), dim3(64), 0, st, p);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+    // phase B over the groups: the same kernel, a group in the place of a chunk (this launch writes logZ)
+    ScanArgs u = a;
+    u.chunk = a.chunk * gs; u.C = G;
+    u.Pl = gb.Pl2; u.rel = gb.rel2; u.base = gb.base2; u.Fv = gb.Fv2; u.OF = gb.OF2; u.Gv = gb.Gv2; u.OG = gb.OG2;
+    hipLaunchKernelGGL(chunk_boundary_kernel<TIN>, dim3(2 * a.B), dim3(64), 0, st, u);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+    // ... and over the chunks of every group at once
+    ScanArgs l = a;
+    l.GS = gs; l.G = G; l.logZ = nullptr; l.logZ64 = nullptr;
+    l.Fin = gb.Fv2; l.OFin = gb.OF2; l.Gin = gb.Gv2; l.OGin = gb.OG2;
+    hipLaunchKernelGGL(chunk_boundary_kernel<TIN>, dim3(2 * a.B * G), dim3(64), 0, st, l);
     return hipGetLastError();
+}
+
+hipError_t launch_scan_boundaries(int dtype, const void* phi, const int32_t* lengths, int B, int N, int T, int chunk,
+                                  float* Pl, float* rel, double* base, float* Fv, double* OF, float* Gv, double* OG,
+                                  const ScanGroupBuffers& gb, float* logZ, bool with_beta, hipStream_t st,
+                                  double* logZ64) {
+    const int C = (N + chunk - 1) / chunk;
+    ScanArgs a{phi, lengths, B, N, T, chunk, C, Pl, rel, base, Fv, OF, Gv, OG, logZ, with_beta ? 1 : 0, logZ64,
+               0, 1, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr};
+    return dtype == 0 ? launch_scan_boundaries_t<float>(a, gb, st) : launch_scan_boundaries_t<uint16_t>(a, gb, st);
 }
 
 
