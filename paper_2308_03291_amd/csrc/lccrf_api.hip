@@ -56,6 +56,7 @@ inline SumWorkspace sum_workspace(size_t B, size_t N, size_t T) {
 struct MaxWorkspace {
     size_t bp, mid;
     size_t Mx, K, pin;  // chunked scan (T <= 16 only, else empty)
+    size_t Mx2, K2, pin2;  // its group level (many chunks only, else empty)
     size_t total;
 };
 inline MaxWorkspace max_workspace(size_t B, size_t N, size_t T) {
@@ -67,6 +68,12 @@ inline MaxWorkspace max_workspace(size_t B, size_t N, size_t T) {
     w.Mx = off; off += round_up(BC * 256 * sizeof(double));
     w.K = off; off += round_up(BC * 16);
     w.pin = off; off += round_up(BC * sizeof(int32_t));
+    const size_t C = (N + g_scan_chunk - 1) / g_scan_chunk;
+    const size_t gs = BC ? (size_t)lccrf::scan_group_size((int)C) : 0;
+    const size_t BG = gs ? B * ((C + gs - 1) / gs) : 0;
+    w.Mx2 = off; off += round_up(BG * 256 * sizeof(double));
+    w.K2 = off; off += round_up(BG * 16);
+    w.pin2 = off; off += round_up(BG * sizeof(int32_t));
     w.total = off;
     return w;
 }
@@ -204,7 +211,10 @@ int lccrf_argmax_algo(const void* phi, lccrf_dtype dt, const int32_t* lengths, i
     if (algo == LCCRF_ALGO_SCAN || (algo == LCCRF_ALGO_AUTO && scan_pays(B, N, T))) {
         int32_t* pin = reinterpret_cast<int32_t*>(base + w.pin);
         e = lccrf::launch_scan_pins(dt, phi, lengths, B, N, T, g_scan_chunk, reinterpret_cast<double*>(base + w.Mx),
-                                    reinterpret_cast<uint8_t*>(base + w.K), pin, best_score, st);
+                                    reinterpret_cast<uint8_t*>(base + w.K), pin,
+                                    {reinterpret_cast<double*>(base + w.Mx2), reinterpret_cast<uint8_t*>(base + w.K2),
+                                     reinterpret_cast<int32_t*>(base + w.pin2)},
+                                    best_score, st);
         if (e == hipSuccess)
             e = lccrf::launch_chunked_max(dt, phi, lengths, B, N, T, bp, mid, tags, g_scan_chunk, pin, st);
     } else {

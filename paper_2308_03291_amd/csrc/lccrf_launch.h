@@ -78,8 +78,14 @@ hipError_t launch_structured_max(const float* emit, const float* trans, const in
 
 // Max-plus chunked scan (lccrf_scan.hip): the best score and the tag of the best path at the last
 // position of every chunk (pin: [B][C] ints).  Mx: [B][C][256] doubles, K: [B][C][16] bytes of scratch.
+struct MaxGroupBuffers {  // group level of the max-plus scan ([B][G]; many chunks only)
+    double* Mx2;
+    uint8_t* K2;
+    int32_t* pin2;
+};
 hipError_t launch_scan_pins(int dtype, const void* phi, const int32_t* lengths, int B, int N, int T, int chunk,
-                            double* Mx, uint8_t* K, int32_t* pin, float* best_score, hipStream_t st);
+                            double* Mx, uint8_t* K, int32_t* pin, const MaxGroupBuffers& gb, float* best_score,
+                            hipStream_t st);
 // Best path inside every chunk between those pinned tags (lccrf_viterbi.hip);
 // mid: viterbi_mid_doubles(B, C, T) doubles of scratch.
 hipError_t launch_chunked_max(int dtype, const void* phi, const int32_t* lengths, int B, int N, int T, uint8_t* bp,

@@ -472,12 +472,57 @@ struct MaxScanArgs {
     uint8_t* K;     // [B][C][16]      best entry tag for each exit tag
     int32_t* pin;   // [B][C]
     float* best_score;
+    // Grouped runs (GS > 0; G = ceil(C / GS) groups a sequence): group_maxplus_kernel writes the
+    // max-plus product of every group's chunk matrices to Mx2 ([B][G][16][16]); the boundary
+    // kernel then handles one group per wave, between the tags pin_in ([B][G]) already fixed at
+    // the last position of every group.
+    int GS, G;
+    double* Mx2;
+    const int32_t* pin_in;
 };
+
+// Max-plus product of matrices first .. last (none: the identity) by one wave.  Lane
+// (r = lane / 4, q = lane % 4) owns M[r][4q .. 4q+3] and stages X_i[r][4q .. 4q+3] of every
+// matrix through LDS.  get(i, jj) returns this lane's four entries of matrix i.
+template <int PF, typename Slot, typename Load, typename Get>
+__device__ __forceinline__ void maxplus_product(int first, int last, int T, double* __restrict__ out, Load load_slot,
+                                                Get get, double (*Mc)[18], double (*Xs)[16]) {
+    const int lane = threadIdx.x, r = lane >> 2, q = lane & 3;
+    const double ninf = -__builtin_huge_val();
+    double M[4];
+#pragma unroll
+    for (int jj = 0; jj < 4; ++jj) M[jj] = (r == 4 * q + jj) ? 0.0 : ninf;
+    Slot ring[PF];
+    auto load = [&](int i, int slot) { load_slot(i, ring[slot]); };
+    walk<PF>(first, last, +1, load, [&](int, int slot) {
+        __syncthreads();
+#pragma unroll
+        for (int jj = 0; jj < 4; ++jj) {
+            Xs[r][4 * q + jj] = get(ring[slot], jj);
+            Mc[r][4 * q + jj] = M[jj];
+        }
+        __syncthreads();
+        double best[4] = {ninf, ninf, ninf, ninf};
+#pragma unroll
+        for (int s = 0; s < 16; ++s) {
+            const double m = Mc[r][s];
+#pragma unroll
+            for (int jj = 0; jj < 4; ++jj) best[jj] = fmax(best[jj], m + Xs[s][4 * q + jj]);
+        }
+#pragma unroll
+        for (int jj = 0; jj < 4; ++jj) M[jj] = best[jj];
+    });
+#pragma unroll
+    for (int jj = 0; jj < 4; ++jj) out[r * 16 + 4 * q + jj] = (r < T && 4 * q + jj < T) ? M[jj] : ninf;
+}
+
+struct MaxSlotF { float x[4]; };
+struct MaxSlotD { double x[4]; };
 
 template <typename TIN>
 __global__ __launch_bounds__(64) void chunk_maxplus_kernel(MaxScanArgs a) {
     __shared__ __attribute__((aligned(16))) double Mc[16][18];
-    __shared__ __attribute__((aligned(16))) float Ph[16][16];
+    __shared__ __attribute__((aligned(16))) double Xs[16][16];
     const int lane = threadIdx.x, r = lane >> 2, q = lane & 3;
     const int b = blockIdx.x / a.C, c = blockIdx.x % a.C;
     const int T = a.T, N = a.N;
@@ -487,8 +532,6 @@ __global__ __launch_bounds__(64) void chunk_maxplus_kernel(MaxScanArgs a) {
     chunk_range(c, a.chunk, L, first, last);
     const size_t TT = (size_t)T * T;
     const TIN* phib = static_cast<const TIN*>(a.phi) + (size_t)b * N * TT;
-    const double ninf = -__builtin_huge_val();
-    // this lane stages phi_i[r][4q .. 4q+3] and owns M[r][4q .. 4q+3]
     int off[4];
     bool in[4];
 #pragma unroll
@@ -497,67 +540,78 @@ __global__ __launch_bounds__(64) void chunk_maxplus_kernel(MaxScanArgs a) {
         in[jj] = r < T && t < T;
         off[jj] = (r < T ? r : T - 1) * T + (t < T ? t : T - 1);
     }
-    double M[4];
+    maxplus_product<kScanPF, MaxSlotF>(
+        first, last, T, a.Mx + ((size_t)b * a.C + c) * 256,
+        [&](int i, MaxSlotF& sl) {
+            const TIN* m = phib + (size_t)i * TT;
 #pragma unroll
-    for (int jj = 0; jj < 4; ++jj) M[jj] = (r == 4 * q + jj) ? 0.0 : ninf;
-    float ring[kScanPF][4];
-    auto load = [&](int i, int slot) {
-        const TIN* m = phib + (size_t)i * TT;
+            for (int jj = 0; jj < 4; ++jj) sl.x[jj] = Elem<TIN>::get(m + off[jj]);
+        },
+        [&](const MaxSlotF& sl, int jj) { return in[jj] ? (double)sl.x[jj] : -__builtin_huge_val(); }, Mc, Xs);
+}
+
+// One wave per group of GS chunks: the max-plus product of the group's chunk matrices.
+__global__ __launch_bounds__(64) void group_maxplus_kernel(MaxScanArgs a) {
+    __shared__ __attribute__((aligned(16))) double Mc[16][18];
+    __shared__ __attribute__((aligned(16))) double Xs[16][16];
+    const int lane = threadIdx.x, r = lane >> 2, q = lane & 3;
+    const int b = blockIdx.x / a.G, g = blockIdx.x % a.G;
+    const int L = clamp_length(a.lengths, b, a.N);
+    const int Cb = (L + a.chunk - 1) / a.chunk;
+    const int c0 = g * a.GS;
+    if (c0 >= Cb) return;
+    const int c1 = (c0 + a.GS < Cb ? c0 + a.GS : Cb) - 1;
+    const double* Mb = a.Mx + (size_t)b * a.C * 256 + r * 16 + 4 * q;
+    maxplus_product<4, MaxSlotD>(
+        c0, c1, a.T, a.Mx2 + ((size_t)b * a.G + g) * 256,
+        [&](int c, MaxSlotD& sl) {
 #pragma unroll
-        for (int jj = 0; jj < 4; ++jj) ring[slot][jj] = Elem<TIN>::get(m + off[jj]);
-    };
-    walk<kScanPF>(first, last, +1, load, [&](int, int slot) {
-        __syncthreads();
-#pragma unroll
-        for (int jj = 0; jj < 4; ++jj) {
-            Ph[r][4 * q + jj] = in[jj] ? ring[slot][jj] : LCCRF_NEG_INF;
-            Mc[r][4 * q + jj] = M[jj];
-        }
-        __syncthreads();
-        double best[4] = {ninf, ninf, ninf, ninf};
-#pragma unroll
-        for (int s = 0; s < 16; ++s) {
-            const double m = Mc[r][s];
-            const float4 f = *reinterpret_cast<const float4*>(&Ph[s][4 * q]);
-            best[0] = fmax(best[0], m + (double)f.x);
-            best[1] = fmax(best[1], m + (double)f.y);
-            best[2] = fmax(best[2], m + (double)f.z);
-            best[3] = fmax(best[3], m + (double)f.w);
-        }
-#pragma unroll
-        for (int jj = 0; jj < 4; ++jj) M[jj] = best[jj];
-    });
-    double* out = a.Mx + ((size_t)b * a.C + c) * 256 + r * 16 + 4 * q;
-#pragma unroll
-    for (int jj = 0; jj < 4; ++jj) out[jj] = (r < T && 4 * q + jj < T) ? M[jj] : ninf;
+            for (int jj = 0; jj < 4; ++jj) sl.x[jj] = Mb[(size_t)c * 256 + jj];
+        },
+        [&](const MaxSlotD& sl, int jj) { return sl.x[jj]; }, Mc, Xs);
 }
 
 constexpr int kPinWindow = 1024;  // chunks of back-pointers held in LDS at a time by the back-trace
 
+// Phase B of the max-plus scan.  One wave per sequence (GS = 0) or per group of chunks (GS > 0):
+// delta through the chunk matrices with the best entry tag per exit tag (K), then the back-trace
+// over those chunks, which fixes the tag at the last position of every chunk (pin).  A whole
+// sequence starts from delta_0 and ends in its best final tag; a group starts from the tag
+// already fixed at the end of the group before it (group 0: delta_0) and ends in the tag fixed at
+// its own end, so what it finds is a best path between those two tags.
 template <typename TIN>
 __global__ __launch_bounds__(64) void chunk_maxplus_boundary_kernel(MaxScanArgs a) {
     __shared__ uint8_t win[kPinWindow * 16];
     const int lane = threadIdx.x, t = lane >> 2, q = lane & 3;
-    const int b = blockIdx.x;
+    const bool grouped = a.GS > 0;
+    const int b = grouped ? blockIdx.x / a.G : blockIdx.x, g = grouped ? blockIdx.x % a.G : 0;
     const int T = a.T, N = a.N;
     const int L = clamp_length(a.lengths, b, N);
     if (L == 0) {
-        if (lane == 0 && a.best_score) a.best_score[b] = 0.f;
+        if (!grouped && lane == 0 && a.best_score) a.best_score[b] = 0.f;
         return;
     }
     const int Cb = (L + a.chunk - 1) / a.chunk;
-    const size_t cb = (size_t)b * a.C;
+    const int c0 = grouped ? g * a.GS : 0;  // chunks c0 .. c1 are this wave's
+    if (c0 >= Cb) return;
+    const int c1 = (grouped && c0 + a.GS < Cb ? c0 + a.GS : Cb) - 1;
+    const size_t cb = (size_t)b * a.C, bg = (size_t)b * a.G;
     const double ninf = -__builtin_huge_val();
-    const TIN* phib = static_cast<const TIN*>(a.phi) + (size_t)b * N * T * T;
     // delta of the last boundary, entry t in lanes 4t .. 4t+3: it travels from step to step in registers
-    double dv = (t < T) ? (double)Elem<TIN>::get(phib + t) : ninf;  // delta_0
+    double dv;
+    if (c0 == 0) {
+        const TIN* phib = static_cast<const TIN*>(a.phi) + (size_t)b * N * T * T;
+        dv = (t < T) ? (double)Elem<TIN>::get(phib + t) : ninf;  // delta_0
+    } else {
+        dv = (t == a.pin_in[bg + g - 1]) ? 0.0 : ninf;  // the tag fixed at the end of the group before
+    }
     double mm[kScanPF][4];
     auto load = [&](int c, int slot) {
         const double* M = a.Mx + (cb + c) * 256;
 #pragma unroll
         for (int jj = 0; jj < 4; ++jj) mm[slot][jj] = M[(4 * q + jj) * 16 + t];
     };
-    walk<kScanPF>(0, Cb - 1, +1, load, [&](int c, int slot) {
+    walk<kScanPF>(c0, c1, +1, load, [&](int c, int slot) {
         double bv = ninf;
         int ba = 0x7fffffff;
         double in[4];
@@ -577,25 +631,32 @@ __global__ __launch_bounds__(64) void chunk_maxplus_boundary_kernel(MaxScanArgs 
         dv = bv;
         if (q == 0) a.K[(cb + c) * 16 + t] = (uint8_t)(ba == 0x7fffffff ? 0 : ba);
     });
-    // best tag at the last position: first maximum (entry t sits in lanes 4t .. 4t+3)
-    double bv = (q == 0 && t < T) ? dv : ninf;
-    int ba = (q == 0 && t < T) ? t : 0x7fffffff;
+    int y;
+    if (!grouped) {
+        // best tag at the last position: first maximum (entry t sits in lanes 4t .. 4t+3)
+        double bv = (q == 0 && t < T) ? dv : ninf;
+        int ba = (q == 0 && t < T) ? t : 0x7fffffff;
 #pragma unroll
-    for (int off = 1; off < 64; off <<= 1) {
-        const double pv = __shfl_xor(bv, off, 64);
-        const int pa = __shfl_xor(ba, off, 64);
-        if (pv > bv || (pv == bv && pa < ba)) { bv = pv; ba = pa; }
+        for (int off = 1; off < 64; off <<= 1) {
+            const double pv = __shfl_xor(bv, off, 64);
+            const int pa = __shfl_xor(ba, off, 64);
+            if (pv > bv || (pv == bv && pa < ba)) { bv = pv; ba = pa; }
+        }
+        if (ba == 0x7fffffff) ba = 0;
+        if (lane == 0 && a.best_score) a.best_score[b] = (float)bv;
+        y = ba;
+    } else {
+        y = a.pin_in[bg + g];
+        if (y < 0 || y >= T) y = 0;
     }
-    if (ba == 0x7fffffff) ba = 0;
-    if (lane == 0 && a.best_score) a.best_score[b] = (float)bv;
     __threadfence();  // K written above is read back below by other lanes
     __syncthreads();
-    // back-trace over chunks through an LDS window of K
-    int y = ba;
-    int hi = Cb;  // chunks [1, hi) still to walk: chunk c maps the tag at its end to the tag at the end of c - 1
-    if (lane == 0) a.pin[cb + Cb - 1] = y;
-    while (hi > 1) {
-        const int lo = (hi - kPinWindow > 1) ? hi - kPinWindow : 1;
+    // back-trace over the chunks through an LDS window of K: chunk c maps the tag at its end to the
+    // tag at the end of chunk c - 1
+    int hi = c1 + 1;  // chunks (c0, hi) still to walk
+    if (lane == 0) a.pin[cb + c1] = y;
+    while (hi > c0 + 1) {
+        const int lo = (hi - kPinWindow > c0 + 1) ? hi - kPinWindow : c0 + 1;
         const int nbytes = (hi - lo) * 16;
         const uint8_t* src = a.K + (cb + lo) * 16;
         for (int k = lane; k < nbytes; k += 64) win[k] = src[k];
@@ -665,21 +726,39 @@ hipError_t launch_scan_boundaries(int dtype, const void* phi, const int32_t* len
 }
 
 
-hipError_t launch_scan_pins(int dtype, const void* phi, const int32_t* lengths, int B, int N, int T, int chunk,
-                            double* Mx, uint8_t* K, int32_t* pin, float* best_score, hipStream_t st) {
-    const int C = (N + chunk - 1) / chunk;
-    MaxScanArgs a{phi, lengths, B, N, T, chunk, C, Mx, K, pin, best_score};
-    if (dtype == 0)
-        hipLaunchKernelGGL(chunk_maxplus_kernel<float>, dim3(B * C), dim3(64), 0, st, a);
-    else
-        hipLaunchKernelGGL(chunk_maxplus_kernel<uint16_t>, dim3(B * C), dim3(64), 0, st, a);
+template <typename TIN>
+static hipError_t launch_scan_pins_t(MaxScanArgs a, const MaxGroupBuffers& gb, hipStream_t st) {
+    hipLaunchKernelGGL(chunk_maxplus_kernel<TIN>, dim3(a.B * a.C), dim3(64), 0, st, a);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    if (dtype == 0)
-        hipLaunchKernelGGL(chunk_maxplus_boundary_kernel<float>, dim3(B), dim3(64), 0, st, a);
-    else
-        hipLaunchKernelGGL(chunk_maxplus_boundary_kernel<uint16_t>, dim3(B), dim3(64), 0, st, a);
+    const int gs = scan_group_size(a.C);
+    if (gs == 0) {
+        hipLaunchKernelGGL(chunk_maxplus_boundary_kernel<TIN>, dim3(a.B), dim3(64), 0, st, a);
+        return hipGetLastError();
+    }
+    const int G = (a.C + gs - 1) / gs;
+    MaxScanArgs p = a;
+    p.GS = gs; p.G = G; p.Mx2 = gb.Mx2;
+    hipLaunchKernelGGL(group_maxplus_kernel, dim3(a.B * G), dim3(64), 0, st, p);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+    // phase B over the groups: the same kernel, a group in the place of a chunk (best score, tags at group ends)
+    MaxScanArgs u = a;
+    u.chunk = a.chunk * gs; u.C = G; u.Mx = gb.Mx2; u.K = gb.K2; u.pin = gb.pin2;
+    hipLaunchKernelGGL(chunk_maxplus_boundary_kernel<TIN>, dim3(a.B), dim3(64), 0, st, u);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+    // ... and inside every group at once, between the tags just fixed
+    MaxScanArgs l = a;
+    l.GS = gs; l.G = G; l.best_score = nullptr; l.pin_in = gb.pin2;
+    hipLaunchKernelGGL(chunk_maxplus_boundary_kernel<TIN>, dim3(a.B * G), dim3(64), 0, st, l);
     return hipGetLastError();
+}
+
+hipError_t launch_scan_pins(int dtype, const void* phi, const int32_t* lengths, int B, int N, int T, int chunk,
+                            double* Mx, uint8_t* K, int32_t* pin, const MaxGroupBuffers& gb, float* best_score,
+                            hipStream_t st) {
+    const int C = (N + chunk - 1) / chunk;
+    MaxScanArgs a{phi, lengths, B, N, T, chunk, C, Mx, K, pin, best_score, 0, 1, nullptr, nullptr};
+    return dtype == 0 ? launch_scan_pins_t<float>(a, gb, st) : launch_scan_pins_t<uint16_t>(a, gb, st);
 }
 
 }  // namespace lccrf
