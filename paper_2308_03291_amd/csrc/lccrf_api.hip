@@ -9,7 +9,7 @@ constexpr size_t kAlign = 256;
 inline size_t round_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 
 // Positions per chunk of the chunked scan (lccrf_set_scan_chunk).
-constexpr int kDefaultScanChunk = 64;
+constexpr int kDefaultScanChunk = 32;
 int g_scan_chunk = kDefaultScanChunk;
 
 struct SumWorkspace {
@@ -105,10 +105,11 @@ int check_common(const void* phi, int dt, int B, int N, int T, const void* ws, s
 }
 
 // Whether LCCRF_ALGO_AUTO takes the chunked scan: the tag set fits its kernels, the chains are long
-// enough for the serial depth to dominate, and the batch alone would not fill the chip.
-inline bool scan_pays(int B, int N, int T) {
-    return lccrf::scan_supported(T) && N >= 8 * g_scan_chunk && (long long)B * N <= (1ll << 22);
-}
+// enough for the serial depth to dominate, and the batch alone would not fill the chip.  Measured:
+// the sequential schedule costs about 0.67 us a position of the longest chain whatever the batch
+// (up to a few waves per SIMD), the scan about 50 us plus 1.1 ns a position of the whole batch,
+// which crosses near 450 sequences for every length from 256 up.
+inline bool scan_pays(int B, int N, int T) { return lccrf::scan_supported(T) && N >= 8 * g_scan_chunk && B <= 448; }
 
 int sum_query(int op, const void* phi, int dt, const int32_t* lengths, int B, int N, int T, float* logZ,
               float* marginals, void* workspace, size_t workspace_bytes, void* stream, int algo,
