@@ -69,7 +69,8 @@ typedef enum {
     LCCRF_ALGO_SCAN = 2,       /* chunked associative scan over positions (the parallel variant the
                                   paper cites in "Sequence Tagging"): products of the T x T matrices
                                   of each chunk, a short serial pass over chunks, then every chunk
-                                  on its own.  Sum queries with T <= 16 only, else LCCRF_ENOTIMPL;
+                                  on its own.  T <= 32 for the sum queries, T <= 16 for lccrf_argmax, else
+                                  LCCRF_ENOTIMPL;
                                   AUTO takes it for long chains in small batches */
     LCCRF_ALGO_SEQUENTIAL_EXACT = 3 /* sequential, and every log-sum-exp shifted by its own maximum:
                                   the step that normally only replays rejected speculative steps

@@ -29,8 +29,9 @@ inline SumWorkspace sum_workspace(size_t B, size_t N, size_t T) {
     w.mail = off; off += round_up(lccrf::pair_mail_words((int)B) * sizeof(unsigned long long));
     w.failed = off; off += round_up(B * sizeof(int));
     const size_t BC = lccrf::scan_supported((int)T) ? B * ((N + g_scan_chunk - 1) / g_scan_chunk) : 0;
-    w.Pl = off; off += round_up(BC * 256 * sizeof(float));
-    w.rel = off; off += round_up(BC * 16 * sizeof(float));
+    const size_t TP = (size_t)lccrf::scan_padded_tags((int)T);
+    w.Pl = off; off += round_up(BC * TP * TP * sizeof(float));
+    w.rel = off; off += round_up(BC * TP * sizeof(float));
     w.base = off; off += round_up(BC * sizeof(double));
     w.Fv = off; off += round_up(BC * T * sizeof(float));
     w.OF = off; off += round_up(BC * sizeof(double));
@@ -39,8 +40,8 @@ inline SumWorkspace sum_workspace(size_t B, size_t N, size_t T) {
     const size_t C = (N + g_scan_chunk - 1) / g_scan_chunk;
     const size_t gs = BC ? (size_t)lccrf::scan_group_size((int)C) : 0;
     const size_t BG = gs ? B * ((C + gs - 1) / gs) : 0;
-    w.Pl2 = off; off += round_up(BG * 256 * sizeof(float));
-    w.rel2 = off; off += round_up(BG * 16 * sizeof(float));
+    w.Pl2 = off; off += round_up(BG * TP * TP * sizeof(float));
+    w.rel2 = off; off += round_up(BG * TP * sizeof(float));
     w.base2 = off; off += round_up(BG * sizeof(double));
     w.Fv2 = off; off += round_up(BG * T * sizeof(float));
     w.OF2 = off; off += round_up(BG * sizeof(double));
@@ -63,7 +64,7 @@ inline MaxWorkspace max_workspace(size_t B, size_t N, size_t T) {
     MaxWorkspace w;
     size_t off = 0;
     w.bp = off; off += round_up(B * N * T);
-    const size_t BC = lccrf::scan_supported((int)T) ? B * ((N + g_scan_chunk - 1) / g_scan_chunk) : 0;
+    const size_t BC = lccrf::scan_supported_max((int)T) ? B * ((N + g_scan_chunk - 1) / g_scan_chunk) : 0;
     w.mid = off; off += round_up((BC > B ? BC : B) * 2 * T * sizeof(double));
     w.Mx = off; off += round_up(BC * 256 * sizeof(double));
     w.K = off; off += round_up(BC * 16);
@@ -105,11 +106,17 @@ int check_common(const void* phi, int dt, int B, int N, int T, const void* ws, s
 }
 
 // Whether LCCRF_ALGO_AUTO takes the chunked scan: the tag set fits its kernels, the chains are long
-// enough for the serial depth to dominate, and the batch alone would not fill the chip.  Measured:
-// the sequential schedule costs about 0.67 us a position of the longest chain whatever the batch
-// (up to a few waves per SIMD), the scan about 50 us plus 1.1 ns a position of the whole batch,
-// which crosses near 450 sequences for every length from 256 up.
-inline bool scan_pays(int B, int N, int T) { return lccrf::scan_supported(T) && N >= 8 * g_scan_chunk && B <= 448; }
+// enough for the serial depth to dominate, and the batch alone would not fill the chip.  Measured
+// for up to 16 tags: the sequential schedule costs about 0.67 us a position of the longest chain
+// whatever the batch (up to a few waves per SIMD), the scan about 50 us plus 1.1 ns a position of
+// the whole batch, which crosses near 450 sequences for every length from 256 up.  For 17 .. 32
+// tags (sum queries only) a chunk product costs eight times the matrix instructions: the scan wins
+// up to about 32768 positions a batch (the paper's own benchmark size, 128 x 256, is the limit).
+inline bool scan_pays(int B, int N, int T) { return lccrf::scan_supported_max(T) && N >= 8 * g_scan_chunk && B <= 448; }
+inline bool scan_pays_sum(int B, int N, int T) {
+    if (scan_pays(B, N, T)) return true;
+    return lccrf::scan_supported(T) && N >= 8 * g_scan_chunk && (long long)B * N <= 32768;
+}
 
 int sum_query(int op, const void* phi, int dt, const int32_t* lengths, int B, int N, int T, float* logZ,
               float* marginals, void* workspace, size_t workspace_bytes, void* stream, int algo,
@@ -127,7 +134,7 @@ int sum_query(int op, const void* phi, int dt, const int32_t* lengths, int B, in
     char* base = static_cast<char*>(workspace);
     hipStream_t st = static_cast<hipStream_t>(stream);
     if (ev_begin && hipEventRecord(static_cast<hipEvent_t>(ev_begin), st) != hipSuccess) return LCCRF_ELAUNCH;
-    if (algo == LCCRF_ALGO_SCAN || (algo == LCCRF_ALGO_AUTO && scan_pays(B, N, T))) {
+    if (algo == LCCRF_ALGO_SCAN || (algo == LCCRF_ALGO_AUTO && scan_pays_sum(B, N, T))) {
         float* Fv = reinterpret_cast<float*>(base + w.Fv);
         double* OF = reinterpret_cast<double*>(base + w.OF);
         float* Gv = reinterpret_cast<float*>(base + w.Gv);
@@ -202,7 +209,7 @@ int lccrf_argmax_algo(const void* phi, lccrf_dtype dt, const int32_t* lengths, i
     if (!tags) return LCCRF_ENULL;
     if (!aligned_to(tags, 4) || (best_score && !aligned_to(best_score, 4))) return LCCRF_EALIGN;
     if (lengths && !aligned_to(lengths, 4)) return LCCRF_EALIGN;
-    if (algo == LCCRF_ALGO_SCAN && !lccrf::scan_supported(T)) return LCCRF_ENOTIMPL;
+    if (algo == LCCRF_ALGO_SCAN && !lccrf::scan_supported_max(T)) return LCCRF_ENOTIMPL;
     const MaxWorkspace w = max_workspace(B, N, T);
     char* base = static_cast<char*>(workspace);
     hipStream_t st = static_cast<hipStream_t>(stream);
@@ -246,7 +253,7 @@ int lccrf_argmax(const void* phi, lccrf_dtype dt, const int32_t* lengths, int B,
 static hipError_t launch_log_partition64(const void* phi, int dt, const int32_t* lengths, int B, int N, int T,
                                          const SumWorkspace& w, char* base, hipStream_t st) {
     double* lz64 = reinterpret_cast<double*>(base + w.lz64);
-    if (scan_pays(B, N, T))
+    if (scan_pays_sum(B, N, T))
         return lccrf::launch_scan_boundaries(
             dt, phi, lengths, B, N, T, g_scan_chunk, reinterpret_cast<float*>(base + w.Pl),
             reinterpret_cast<float*>(base + w.rel), reinterpret_cast<double*>(base + w.base),

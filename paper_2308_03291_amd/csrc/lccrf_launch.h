@@ -41,7 +41,9 @@ hipError_t launch_pair_marginals(int dtype, const void* phi, const int32_t* leng
 // double), and logZ if non-null.  with_beta false: forward vectors and logZ only.
 // With many chunks the serial pass over chunks is itself split into groups of scan_group_size(C) chunks
 // (0: not split); the group-level copies of the arrays above ([B][G], G = ceil(C / group size)) live in gb.
-bool scan_supported(int T);
+bool scan_supported(int T);      // sum queries (T <= 32)
+bool scan_supported_max(int T);  // lccrf_argmax (T <= 16)
+int scan_padded_tags(int T);     // 16 or 32: side of the stored chunk matrices
 int scan_group_size(int C);
 struct ScanGroupBuffers {
     float* Pl2;

@@ -48,9 +48,9 @@ struct ScanArgs {
     int B, N, T;
     int chunk, C;
     // log2 P_c[r][s] = Pl[b][c][s][r] + rel[b][c][r] + base[b][c]   (r: entry tag, s: exit tag;
-    // tags >= T are padded with -inf)
-    float* Pl;     // [B][C][16][16]
-    float* rel;    // [B][C][16]  integer valued, <= 0
+    // tags >= T are padded with -inf up to TP = 16 or 32, the padded tag count of the launch)
+    float* Pl;     // [B][C][TP][TP]
+    float* rel;    // [B][C][TP]  integer valued, <= 0
     double* base;  // [B][C]
     float* Fv;     // [B][C][T]   alpha at the last position of chunk c, maximum 0 ...
     double* OF;    // [B][C]      ... plus this offset (base-2 logarithms)
@@ -84,35 +84,47 @@ __device__ __forceinline__ void chunk_range(int c, int chunk, int L, int& first,
 // ---------------------------------------------------------------------------------------
 // Phase A.
 //
-// Where the matrices of a product come from.  Lane (g = lane / 16, j = lane % 16) handles the
-// entries M_i[g + 4v][j], v = 0..3, of matrix i (row: tag before, column: tag after), in base-2
-// logarithms, -inf outside T x T; every matrix may carry a common offset besides.
-template <typename TIN>
+// TP is the padded tag count (16 or 32); matrices are handled as NB x NB blocks of 16 x 16,
+// NB = TP / 16.  Lane (g = lane / 16, j = lane % 16) handles, of block (sb, tb), the entries
+// M[16 sb + g + 4v][16 tb + j], v = 0..3 (row: tag before, column: tag after); entry number
+// e = (sb NB + tb) 4 + v.  Sources hand out matrices in base-2 logarithms, -inf outside T x T;
+// every matrix may carry a common offset besides.
+template <int TP>
+struct ScanShape {
+    static constexpr int NB = TP / 16, NE = 4 * NB * NB;
+    static constexpr int LPRow = 64 / TP;    // lanes sharing a row in the row-wise layouts (exact product, phase B)
+    static constexpr int CPL = TP / LPRow;   // columns per lane there
+    static_assert(TP == 16 || TP == 32, "padded tag count");
+    static __device__ __forceinline__ int row(int lane, int e) { return 16 * (e / (4 * NB)) + (lane >> 4) + 4 * (e & 3); }
+    static __device__ __forceinline__ int col(int lane, int e) { return 16 * ((e / 4) % NB) + (lane & 15); }
+};
+
+template <typename TIN, int TP>
 struct PotentialMatrices {  // the potentials phi_i of one sequence
-    static constexpr int PF = kScanPF;
-    struct Slot { float x[4]; };
+    using S = ScanShape<TP>;
+    static constexpr int PF = TP == 16 ? kScanPF : 3;
+    struct Slot { float x[S::NE]; };
     const TIN* phib;
     int T;
     size_t TT;
-    int off[4];
-    bool in[4];
-    __device__ PotentialMatrices(const TIN* p, int T_, int lane) : phib(p), T(T_), TT((size_t)T_ * T_) {
-        const int g = lane >> 4, j = lane & 15;
+    int off[S::NE];
+    unsigned in;  // bit e: entry e lies inside T x T
+    __device__ PotentialMatrices(const TIN* p, int T_, int lane) : phib(p), T(T_), TT((size_t)T_ * T_), in(0) {
 #pragma unroll
-        for (int v = 0; v < 4; ++v) {
-            const int s = g + 4 * v;
-            in[v] = s < T && j < T;
-            off[v] = (s < T ? s : T - 1) * T + (j < T ? j : T - 1);
+        for (int e = 0; e < S::NE; ++e) {
+            const int s = S::row(lane, e), t = S::col(lane, e);
+            in |= (s < T && t < T) ? (1u << e) : 0u;
+            off[e] = (s < T ? s : T - 1) * T + (t < T ? t : T - 1);
         }
     }
     __device__ __forceinline__ void load(int i, Slot& sl) const {
         const TIN* m = phib + (size_t)i * TT;
 #pragma unroll
-        for (int v = 0; v < 4; ++v) sl.x[v] = Elem<TIN>::get(m + off[v]);
+        for (int e = 0; e < S::NE; ++e) sl.x[e] = Elem<TIN>::get(m + off[e]);
     }
-    __device__ __forceinline__ double entries(const Slot& sl, float (&x)[4]) const {
+    __device__ __forceinline__ double entries(const Slot& sl, float (&x)[S::NE]) const {
 #pragma unroll
-        for (int v = 0; v < 4; ++v) x[v] = in[v] ? sl.x[v] * kLog2e : LCCRF_NEG_INF;
+        for (int e = 0; e < S::NE; ++e) x[e] = (in >> e) & 1 ? sl.x[e] * kLog2e : LCCRF_NEG_INF;
         return 0.0;
     }
     __device__ __forceinline__ float entry(int i, int r, int t) const {  // one entry, straight from memory
@@ -121,188 +133,270 @@ struct PotentialMatrices {  // the potentials phi_i of one sequence
     __device__ __forceinline__ double offset(int) const { return 0.0; }
 };
 
+template <int TP>
 struct ChunkMatrices {  // the chunk products of one sequence, as phase A has written them
-    static constexpr int PF = 4;
-    struct Slot { float p[4], r[4]; double b; };
+    using S = ScanShape<TP>;
+    static constexpr int PF = TP == 16 ? 4 : 2;
+    struct Slot { float p[S::NE], r[S::NE]; double b; };
     const float* Pl;
     const float* rel;
     const double* base;
-    int T, g, j;
-    __device__ ChunkMatrices(const float* Pl_, const float* rel_, const double* base_, int T_, int lane)
-        : Pl(Pl_), rel(rel_), base(base_), T(T_), g(lane >> 4), j(lane & 15) {}
+    int T, lane;
+    __device__ ChunkMatrices(const float* Pl_, const float* rel_, const double* base_, int T_, int lane_)
+        : Pl(Pl_), rel(rel_), base(base_), T(T_), lane(lane_) {}
     __device__ __forceinline__ void load(int c, Slot& sl) const {
 #pragma unroll
-        for (int v = 0; v < 4; ++v) {
-            sl.p[v] = Pl[(size_t)c * 256 + j * 16 + g + 4 * v];
-            sl.r[v] = rel[(size_t)c * 16 + g + 4 * v];
+        for (int e = 0; e < S::NE; ++e) {
+            sl.p[e] = Pl[(size_t)c * TP * TP + S::col(lane, e) * TP + S::row(lane, e)];
+            sl.r[e] = rel[(size_t)c * TP + S::row(lane, e)];
         }
         sl.b = base[c];
     }
-    __device__ __forceinline__ double entries(const Slot& sl, float (&x)[4]) const {
+    __device__ __forceinline__ double entries(const Slot& sl, float (&x)[S::NE]) const {
 #pragma unroll
-        for (int v = 0; v < 4; ++v) x[v] = (g + 4 * v < T && j < T) ? sl.p[v] + sl.r[v] : LCCRF_NEG_INF;
+        for (int e = 0; e < S::NE; ++e)
+            x[e] = (S::row(lane, e) < T && S::col(lane, e) < T) ? sl.p[e] + sl.r[e] : LCCRF_NEG_INF;
         return sl.b;
     }
     __device__ __forceinline__ float entry(int c, int r, int t) const {
-        return (r < T && t < T) ? Pl[(size_t)c * 256 + t * 16 + r] + rel[(size_t)c * 16 + r] : LCCRF_NEG_INF;
+        return (r < T && t < T) ? Pl[(size_t)c * TP * TP + t * TP + r] + rel[(size_t)c * TP + r] : LCCRF_NEG_INF;
     }
     __device__ __forceinline__ double offset(int c) const { return base[c]; }
 };
 
 // Product of matrices first .. last of `src` (none: the identity), by one wave, written as
-// log2 P[r][s] = Pout[s * 16 + r] + rel_out[r] + *base_out.
-template <typename Src>
+// log2 P[r][s] = Pout[s * TP + r] + rel_out[r] + *base_out.
+template <int TP, typename Src>
 __device__ __forceinline__ void matrix_product(const Src& src, int first, int last, int T, float* __restrict__ Pout,
                                                float* __restrict__ rel_out, double* __restrict__ base_out,
-                                               float (*Pc)[17], float (*Ph)[17]) {
+                                               float (*Pc)[TP + 1], float (*Ph)[TP + 1]) {
+    using S = ScanShape<TP>;
+    constexpr int NB = S::NB, NE = S::NE;
     const int lane = threadIdx.x;
     // ---- linear-domain product on the matrix cores, in double precision for its exponent range.
-    // D[s][r] (exit tag s, entry tag r) sits in the accumulator layout of the 16x16x4 f64 MFMA:
-    // lane (g = lane / 16, j = lane % 16) holds D[g + 4v][j], v = 0..3.  The same lane loads
-    // phi_i[g + 4v][j]; as the A operand of MFMA number v that is E^T[j][k = g] for the inner
-    // index s = g + 4v, and D's own register v is the matching B operand, so
-    //     D_new[t][r] = sum_v sum_g E[g + 4v][t] D[g + 4v][r] = sum_s E[s][t] D[s][r]
-    // needs no data movement between positions.
+    // Block (sb, rb) of D (exit tag s, entry tag r) sits in the accumulator layout of the 16x16x4
+    // f64 MFMA: lane (g, j) holds D[16 sb + g + 4v][16 rb + j], v = 0..3.  The same lane loads
+    // phi_i[16 sb + g + 4v][16 tb + j]; as the A operand of an MFMA that is E^T[j][k = g] for the
+    // inner indices s = 16 sb + g + 4v, and register v of D's block (sb, rb) is the matching B
+    // operand, so block (tb, rb) of
+    //     D_new[t][r] = sum_s E[s][t] D[s][r]
+    // is the sum over sb and v of those MFMAs, and nothing moves between lanes from one position
+    // to the next.
     {
         const int g = lane >> 4, j = lane & 15;
-        bool in[4];
+        unsigned in = 0;
 #pragma unroll
-        for (int v = 0; v < 4; ++v) in[v] = g + 4 * v < T && j < T;
+        for (int e = 0; e < NE; ++e) in |= (S::row(lane, e) < T && S::col(lane, e) < T) ? (1u << e) : 0u;
         // The zero pattern of D (1 where some path exists) is carried along by a product of 0/1
         // matrices on the f32 MFMA, from the first matrix with a -inf entry on (until then D is
         // the identity or has no zero).  That instruction numbers its output rows 4g + v, so it
         // runs on rows renamed by pi(4g + v) = g + 4v: its A operand is the flag of column pi(j).
         const int pj = (lane & 48) | (4 * (j & 3) + (j >> 2));
-        double D[4];
-        float Z[4];
+        double D[NB][NB][4];
+        float Z[NB][NB][4];
 #pragma unroll
-        for (int v = 0; v < 4; ++v) {
-            D[v] = (g + 4 * v == j) ? 1.0 : 0.0;
-            Z[v] = (g + 4 * v == j) ? 1.f : 0.f;
-        }
+        for (int sb = 0; sb < NB; ++sb)
+#pragma unroll
+            for (int rb = 0; rb < NB; ++rb)
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    const bool diag = sb == rb && g + 4 * v == j;
+                    D[sb][rb][v] = diag ? 1.0 : 0.0;
+                    Z[sb][rb][v] = diag ? 1.f : 0.f;
+                }
         typename Src::Slot ring[Src::PF];
         auto load = [&](int i, int slot) { src.load(i, ring[slot]); };
         double Msum = 0.0;
-        int esum = 0;
+        int esum[NB];
+#pragma unroll
+        for (int rb = 0; rb < NB; ++rb) esum[rb] = 0;
         bool bad = false, tracking = false, started = false;
         walk<Src::PF>(first, last, +1, load, [&](int, int slot) {
-            float x[4];
+            float x[NE];
             const double common = src.entries(ring[slot], x);
-            const float m = finite_or_zero(xor_max<1, 64>(fmaxf(fmaxf(x[0], x[1]), fmaxf(x[2], x[3]))));
-            Msum += (double)m + common;
-            int nz = 0;
-            f64x4 acc = {0.0, 0.0, 0.0, 0.0};
+            float mloc = x[0];
 #pragma unroll
-            for (int v = 0; v < 4; ++v) {
-                // E = 2^(x - m) in double: the fraction through the float exponential, the integer
-                // part through the exponent field
-                const float d = x[v] - m, di = floorf(d);
-                const double E = d > -1000.f ? ldexp((double)ex2(d - di), (int)di) : 0.0;
-                nz |= (x[v] > LCCRF_NEG_INF) ? (1 << v) : 0;
-                acc = __builtin_amdgcn_mfma_f64_16x16x4f64(E, D[v], acc, 0, 0, 0);
-            }
-            const bool hole = (in[0] && !(nz & 1)) || (in[1] && !(nz & 2)) || (in[2] && !(nz & 4)) || (in[3] && !(nz & 8));
+            for (int e = 1; e < NE; ++e) mloc = fmaxf(mloc, x[e]);
+            const float m = finite_or_zero(xor_max<1, 64>(mloc));
+            Msum += (double)m + common;
+            unsigned nz = 0;
+            f64x4 acc[NB][NB];
+#pragma unroll
+            for (int tb = 0; tb < NB; ++tb)
+#pragma unroll
+                for (int rb = 0; rb < NB; ++rb) acc[tb][rb] = f64x4{0.0, 0.0, 0.0, 0.0};
+#pragma unroll
+            for (int sb = 0; sb < NB; ++sb)
+#pragma unroll
+                for (int tb = 0; tb < NB; ++tb)
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) {
+                        const int e = (sb * NB + tb) * 4 + v;
+                        // E = 2^(x - m) in double: the fraction through the float exponential, the
+                        // integer part through the exponent field
+                        const float d = x[e] - m, di = floorf(d);
+                        const double E = d > -1000.f ? ldexp((double)ex2(d - di), (int)di) : 0.0;
+                        nz |= (x[e] > LCCRF_NEG_INF) ? (1u << e) : 0u;
+#pragma unroll
+                        for (int rb = 0; rb < NB; ++rb)
+                            acc[tb][rb] = __builtin_amdgcn_mfma_f64_16x16x4f64(E, D[sb][rb][v], acc[tb][rb], 0, 0, 0);
+                    }
+            const bool hole = (in & ~nz) != 0;
             if (!tracking && __builtin_amdgcn_ballot_w64(hole) != 0) {
                 tracking = true;
                 if (started) {
 #pragma unroll
-                    for (int v = 0; v < 4; ++v) Z[v] = in[v] ? 1.f : 0.f;
+                    for (int sb = 0; sb < NB; ++sb)
+#pragma unroll
+                        for (int rb = 0; rb < NB; ++rb)
+#pragma unroll
+                            for (int v = 0; v < 4; ++v) Z[sb][rb][v] = (in >> ((sb * NB + rb) * 4 + v)) & 1 ? 1.f : 0.f;
                 }
             }
             started = true;
             if (tracking) {
-                const int nzp = __shfl(nz, pj, 64);
-                f32x4 pat = {0.f, 0.f, 0.f, 0.f};
+                const unsigned nzp = (unsigned)__shfl((int)nz, pj, 64);
+                f32x4 pat[NB][NB];
 #pragma unroll
-                for (int v = 0; v < 4; ++v)
-                    pat = __builtin_amdgcn_mfma_f32_16x16x4f32((nzp >> v) & 1 ? 1.f : 0.f, Z[v], pat, 0, 0, 0);
+                for (int tb = 0; tb < NB; ++tb)
 #pragma unroll
-                for (int v = 0; v < 4; ++v) {
-                    Z[v] = pat[v] > 0.f ? 1.f : 0.f;
-                    bad |= (pat[v] > 0.f) & !(acc[v] >= kTiny);
-                }
+                    for (int rb = 0; rb < NB; ++rb) pat[tb][rb] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int sb = 0; sb < NB; ++sb)
+#pragma unroll
+                    for (int tb = 0; tb < NB; ++tb)
+#pragma unroll
+                        for (int v = 0; v < 4; ++v) {
+                            const float flag = (nzp >> ((sb * NB + tb) * 4 + v)) & 1 ? 1.f : 0.f;
+#pragma unroll
+                            for (int rb = 0; rb < NB; ++rb)
+                                pat[tb][rb] = __builtin_amdgcn_mfma_f32_16x16x4f32(flag, Z[sb][rb][v], pat[tb][rb], 0, 0, 0);
+                        }
+#pragma unroll
+                for (int tb = 0; tb < NB; ++tb)
+#pragma unroll
+                    for (int rb = 0; rb < NB; ++rb)
+#pragma unroll
+                        for (int v = 0; v < 4; ++v) {
+                            Z[tb][rb][v] = pat[tb][rb][v] > 0.f ? 1.f : 0.f;
+                            bad |= (pat[tb][rb][v] > 0.f) & !(acc[tb][rb][v] >= kTiny);
+                        }
             } else {
 #pragma unroll
-                for (int v = 0; v < 4; ++v) bad |= in[v] & !(acc[v] >= kTiny);
+                for (int tb = 0; tb < NB; ++tb)
+#pragma unroll
+                    for (int rb = 0; rb < NB; ++rb)
+#pragma unroll
+                        for (int v = 0; v < 4; ++v)
+                            bad |= ((in >> ((tb * NB + rb) * 4 + v)) & 1) & !(acc[tb][rb][v] >= kTiny);
             }
             // With the column maxima of D in [1, 2) and E at most 1, a term lost to underflow is
             // below 2^-1022: it cannot matter to a sum that is at least kTiny.
             // Power-of-two rescale of each entry tag's column (exact): the largest exponent field.
-            int ef = 0;
 #pragma unroll
-            for (int v = 0; v < 4; ++v) {
-                const int f = (__double2hiint(acc[v]) >> 20) & 0x7ff;
-                ef = f > ef ? f : ef;
-            }
-            {
+            for (int rb = 0; rb < NB; ++rb) {
+                int ef = 0;
+#pragma unroll
+                for (int tb = 0; tb < NB; ++tb)
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) {
+                        const int f = (__double2hiint(acc[tb][rb][v]) >> 20) & 0x7ff;
+                        ef = f > ef ? f : ef;
+                    }
                 const auto r16 = __builtin_amdgcn_permlane16_swap(ef, ef, false, false);
                 ef = (int)r16[0] > (int)r16[1] ? (int)r16[0] : (int)r16[1];
                 const auto r32 = __builtin_amdgcn_permlane32_swap(ef, ef, false, false);
                 ef = (int)r32[0] > (int)r32[1] ? (int)r32[0] : (int)r32[1];
-            }
-            const int ex = ef > 0 ? ef - 1023 : 0;
-            esum += ex;
+                const int ex = ef > 0 ? ef - 1023 : 0;
+                esum[rb] += ex;
 #pragma unroll
-            for (int v = 0; v < 4; ++v) D[v] = ldexp(acc[v], -ex);
+                for (int tb = 0; tb < NB; ++tb)
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) D[tb][rb][v] = ldexp(acc[tb][rb][v], -ex);
+            }
         });
         if (__builtin_amdgcn_ballot_w64(bad) == 0) {
-            const float ef = j < T ? (float)esum : LCCRF_NEG_INF;
-            const float emax = finite_or_zero(xor_max<1, 16>(ef));
+            float ef[NB], emax = LCCRF_NEG_INF;
 #pragma unroll
-            for (int v = 0; v < 4; ++v)
-                Pout[(g + 4 * v) * 16 + j] = (in[v] && D[v] > 0.0) ? (float)log2(D[v]) : LCCRF_NEG_INF;
-            if (g == 0) rel_out[j] = ef - emax;
+            for (int rb = 0; rb < NB; ++rb) {
+                ef[rb] = 16 * rb + j < T ? (float)esum[rb] : LCCRF_NEG_INF;
+                emax = fmaxf(emax, xor_max<1, 16>(ef[rb]));
+            }
+            emax = finite_or_zero(emax);
+#pragma unroll
+            for (int tb = 0; tb < NB; ++tb)
+#pragma unroll
+                for (int rb = 0; rb < NB; ++rb)
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) {
+                        const bool inside = (in >> ((tb * NB + rb) * 4 + v)) & 1;
+                        Pout[(16 * tb + g + 4 * v) * TP + 16 * rb + j] =
+                            (inside && D[tb][rb][v] > 0.0) ? (float)log2(D[tb][rb][v]) : LCCRF_NEG_INF;
+                    }
+            if (g == 0) {
+#pragma unroll
+                for (int rb = 0; rb < NB; ++rb) rel_out[16 * rb + j] = ef[rb] - emax;
+            }
             if (lane == 0) *base_out = Msum + (double)emax;
             return;
         }
     }
 
-    // ---- exact log-domain product (rare).  Lane (r = lane / 4, q = lane % 4) owns
-    // P[r][4q .. 4q+3]; P and the current matrix are exchanged through LDS.
+    // ---- exact log-domain product (rare).  Lane (r = lane / LPRow, q = lane % LPRow) owns
+    // P[r][CPL q .. CPL q + CPL - 1]; P and the current matrix are exchanged through LDS.
     {
-        const int r = lane >> 2, q = lane & 3;
-        float out[4];
+        constexpr int LPRow = S::LPRow, CPL = S::CPL;
+        const int r = lane / LPRow, q = lane % LPRow;
+        float out[CPL];
 #pragma unroll
-        for (int jj = 0; jj < 4; ++jj) out[jj] = (r == 4 * q + jj) ? 0.f : LCCRF_NEG_INF;
+        for (int jj = 0; jj < CPL; ++jj) out[jj] = (r == CPL * q + jj) ? 0.f : LCCRF_NEG_INF;
         float sg = 0.f;  // integer valued
         double osum = 0.0;
         for (int i = first; i <= last; ++i) {
             osum += src.offset(i);
             __syncthreads();
 #pragma unroll
-            for (int jj = 0; jj < 4; ++jj) {
-                const int t = 4 * q + jj;
+            for (int jj = 0; jj < CPL; ++jj) {
+                const int t = CPL * q + jj;
                 Pc[r][t] = out[jj];
                 Ph[r][t] = src.entry(i, r, t);
             }
             __syncthreads();
-            float mx[4] = {LCCRF_NEG_INF, LCCRF_NEG_INF, LCCRF_NEG_INF, LCCRF_NEG_INF};
-            for (int s = 0; s < 16; ++s) {
+            float mx[CPL], sm[CPL];
+#pragma unroll
+            for (int jj = 0; jj < CPL; ++jj) {
+                mx[jj] = LCCRF_NEG_INF;
+                sm[jj] = 0.f;
+            }
+            for (int s = 0; s < TP; ++s) {
                 const float p = Pc[r][s];
 #pragma unroll
-                for (int jj = 0; jj < 4; ++jj) mx[jj] = fmaxf(mx[jj], p + Ph[s][4 * q + jj]);
+                for (int jj = 0; jj < CPL; ++jj) mx[jj] = fmaxf(mx[jj], p + Ph[s][CPL * q + jj]);
             }
-            float sm[4] = {0.f, 0.f, 0.f, 0.f};
-            for (int s = 0; s < 16; ++s) {
+            for (int s = 0; s < TP; ++s) {
                 const float p = Pc[r][s];
 #pragma unroll
-                for (int jj = 0; jj < 4; ++jj) sm[jj] += ex2(p + Ph[s][4 * q + jj] - finite_or_zero(mx[jj]));
+                for (int jj = 0; jj < CPL; ++jj) sm[jj] += ex2(p + Ph[s][CPL * q + jj] - finite_or_zero(mx[jj]));
             }
+            float rm = LCCRF_NEG_INF;
 #pragma unroll
-            for (int jj = 0; jj < 4; ++jj) out[jj] = mx[jj] + lg2(sm[jj]);
+            for (int jj = 0; jj < CPL; ++jj) {
+                out[jj] = mx[jj] + lg2(sm[jj]);
+                rm = fmaxf(rm, out[jj]);
+            }
             // shift the row by the integer part of its maximum: scales stay integers, hence exact
-            const float rm = xor_max<1, 4>(fmaxf(fmaxf(out[0], out[1]), fmaxf(out[2], out[3])));
+            rm = xor_max<1, LPRow>(rm);
             const float sh = floorf(finite_or_zero(rm));
             sg += sh;
 #pragma unroll
-            for (int jj = 0; jj < 4; ++jj) out[jj] -= sh;
+            for (int jj = 0; jj < CPL; ++jj) out[jj] -= sh;
         }
         const float ef = r < T ? sg : LCCRF_NEG_INF;
-        const float emax = finite_or_zero(xor_max<4, 64>(ef));
+        const float emax = finite_or_zero(xor_max<LPRow, 64>(ef));
 #pragma unroll
-        for (int jj = 0; jj < 4; ++jj) {
-            const int t = 4 * q + jj;
-            Pout[t * 16 + r] = (r < T && t < T) ? out[jj] : LCCRF_NEG_INF;
+        for (int jj = 0; jj < CPL; ++jj) {
+            const int t = CPL * q + jj;
+            Pout[t * TP + r] = (r < T && t < T) ? out[jj] : LCCRF_NEG_INF;
         }
         if (q == 0) rel_out[r] = ef - emax;
         if (lane == 0) *base_out = osum + (double)emax;
@@ -310,25 +404,26 @@ __device__ __forceinline__ void matrix_product(const Src& src, int first, int la
 }
 
 // One wave per chunk: the product of the chunk's potentials.
-template <typename TIN>
+template <typename TIN, int TP>
 __global__ __launch_bounds__(64) void chunk_product_kernel(ScanArgs a) {
-    __shared__ float Pc[16][17];
-    __shared__ float Ph[16][17];
+    __shared__ float Pc[TP][TP + 1];
+    __shared__ float Ph[TP][TP + 1];
     const int b = blockIdx.x / a.C, c = blockIdx.x % a.C;
     const int T = a.T, N = a.N;
     const int L = clamp_length(a.lengths, b, N);
     if (c * a.chunk >= L) return;
     int first, last;
     chunk_range(c, a.chunk, L, first, last);
-    const PotentialMatrices<TIN> src(static_cast<const TIN*>(a.phi) + (size_t)b * N * T * T, T, threadIdx.x);
+    const PotentialMatrices<TIN, TP> src(static_cast<const TIN*>(a.phi) + (size_t)b * N * T * T, T, threadIdx.x);
     const size_t bc = (size_t)b * a.C + c;
-    matrix_product(src, first, last, T, a.Pl + bc * 256, a.rel + bc * 16, a.base + bc, Pc, Ph);
+    matrix_product<TP>(src, first, last, T, a.Pl + bc * TP * TP, a.rel + bc * TP, a.base + bc, Pc, Ph);
 }
 
 // One wave per group of GS chunks: the product of the group's chunk products.
+template <int TP>
 __global__ __launch_bounds__(64) void group_product_kernel(ScanArgs a) {
-    __shared__ float Pc[16][17];
-    __shared__ float Ph[16][17];
+    __shared__ float Pc[TP][TP + 1];
+    __shared__ float Ph[TP][TP + 1];
     const int b = blockIdx.x / a.G, g = blockIdx.x % a.G;
     const int L = clamp_length(a.lengths, b, a.N);
     const int Cb = (L + a.chunk - 1) / a.chunk;  // chunks of this sequence
@@ -336,22 +431,25 @@ __global__ __launch_bounds__(64) void group_product_kernel(ScanArgs a) {
     if (c0 >= Cb) return;
     const int c1 = (c0 + a.GS < Cb ? c0 + a.GS : Cb) - 1;
     const size_t cb = (size_t)b * a.C, bg = (size_t)b * a.G + g;
-    const ChunkMatrices src(a.Pl + cb * 256, a.rel + cb * 16, a.base + cb, a.T, threadIdx.x);
-    matrix_product(src, c0, c1, a.T, a.Pl2 + bg * 256, a.rel2 + bg * 16, a.base2 + bg, Pc, Ph);
+    const ChunkMatrices<TP> src(a.Pl + cb * TP * TP, a.rel + cb * TP, a.base + cb, a.T, threadIdx.x);
+    matrix_product<TP>(src, c0, c1, a.T, a.Pl2 + bg * TP * TP, a.rel2 + bg * TP, a.base2 + bg, Pc, Ph);
 }
 
 // ---------------------------------------------------------------------------------------
 // Phase B.  One wave runs the forward vector through a run of chunk products, another the
 // backward vector: the whole sequence (GS = 0: waves 2b and 2b + 1), or the chunks of one group
 // (GS > 0: waves 2 (b G + g) and 2 (b G + g) + 1), started from the boundary vectors of the
-// groups.  Lane (o = lane / 4, q = lane % 4) produces output entry o from the four input entries
-// 4q .. 4q+3; the vector travels from step to step in registers: entry t of the new vector sits in
-// lanes 4t .. 4t+3, lane (o, q) fetches entries 4q .. 4q+3 with four lane reads.  It is normalised
-// by the maximum of the PREVIOUS vector (one step stale: consecutive maxima differ little), so
-// the wave-wide maximum is off the chain of dependent instructions.
-template <typename TIN>
+// groups.  Lane (o = lane / LPRow, q = lane % LPRow) produces output entry o from the CPL input
+// entries CPL q .. CPL q + CPL - 1; the vector travels from step to step in registers: entry t of
+// the new vector sits in lanes LPRow t .. LPRow t + LPRow - 1, a lane fetches its input entries
+// with lane reads.  It is normalised by the maximum of the PREVIOUS vector (one step stale:
+// consecutive maxima differ little), so the wave-wide maximum is off the chain of dependent
+// instructions.
+template <typename TIN, int TP>
 __global__ __launch_bounds__(64) void chunk_boundary_kernel(ScanArgs a) {
-    const int lane = threadIdx.x, o = lane >> 2, q = lane & 3;
+    using S = ScanShape<TP>;
+    constexpr int LPRow = S::LPRow, CPL = S::CPL, PF = TP == 16 ? kScanPF : 4;
+    const int lane = threadIdx.x, o = lane / LPRow, q = lane % LPRow;
     const int dir = blockIdx.x & 1;
     const int unit = blockIdx.x >> 1;
     const bool grouped = a.GS > 0;
@@ -370,9 +468,21 @@ __global__ __launch_bounds__(64) void chunk_boundary_kernel(ScanArgs a) {
     const int c1 = (grouped && c0 + a.GS < Cb ? c0 + a.GS : Cb) - 1;
     const size_t cb = (size_t)b * a.C, bg = (size_t)b * a.G;
     double O = 0.0;
+    // one step: x[jj] holds (input entry) + (matrix entry); returns log2 of the sum of their powers
+    auto lse = [&](const float (&x)[CPL]) {
+        float mx = x[0];
+#pragma unroll
+        for (int jj = 1; jj < CPL; ++jj) mx = fmaxf(mx, x[jj]);
+        mx = xor_max<1, LPRow>(mx);
+        const float mf = finite_or_zero(mx);
+        float s = 0.f;
+#pragma unroll
+        for (int jj = 0; jj < CPL; ++jj) s += ex2(x[jj] - mf);
+        return mx + lg2(xor_sum<1, LPRow>(s));
+    };
 
     if (dir == 0) {
-        float nv;  // alpha before chunk c0, entry o in lanes 4o .. 4o+3
+        float nv;  // alpha before chunk c0, entry o in lanes LPRow o ..
         if (c0 == 0) {
             const TIN* phib = static_cast<const TIN*>(a.phi) + (size_t)b * N * T * T;
             const float v = (lane < T) ? Elem<TIN>::get(phib + lane) * kLog2e : LCCRF_NEG_INF;  // alpha_0
@@ -383,40 +493,41 @@ __global__ __launch_bounds__(64) void chunk_boundary_kernel(ScanArgs a) {
             nv = (o < T) ? a.Fin[(bg + g - 1) * T + o] : LCCRF_NEG_INF;
             O = a.OFin[bg + g - 1];
         }
-        float pm[kScanPF][4], rl[kScanPF][4];
-        double bs[kScanPF];
+        float pm[PF][CPL], rl[PF][CPL];
+        double bs[PF];
         auto load = [&](int c, int slot) {
-            const float4 p = *reinterpret_cast<const float4*>(a.Pl + (cb + c) * 256 + o * 16 + 4 * q);
-            const float4 e = *reinterpret_cast<const float4*>(a.rel + (cb + c) * 16 + 4 * q);
-            pm[slot][0] = p.x; pm[slot][1] = p.y; pm[slot][2] = p.z; pm[slot][3] = p.w;
-            rl[slot][0] = e.x; rl[slot][1] = e.y; rl[slot][2] = e.z; rl[slot][3] = e.w;
+            const float* P = a.Pl + (cb + c) * TP * TP + o * TP + CPL * q;
+            const float* E = a.rel + (cb + c) * TP + CPL * q;
+#pragma unroll
+            for (int k = 0; k < CPL; k += 4) {
+                const float4 p = *reinterpret_cast<const float4*>(P + k);
+                const float4 e = *reinterpret_cast<const float4*>(E + k);
+                pm[slot][k] = p.x; pm[slot][k + 1] = p.y; pm[slot][k + 2] = p.z; pm[slot][k + 3] = p.w;
+                rl[slot][k] = e.x; rl[slot][k + 1] = e.y; rl[slot][k + 2] = e.z; rl[slot][k + 3] = e.w;
+            }
             bs[slot] = a.base[cb + c];
         };
         float dprev = 0.f;
-        walk<kScanPF>(c0, c1, +1, load, [&](int c, int slot) {
-            const float f0 = lane_bperm(nv, 16 * q), f1 = lane_bperm(nv, 16 * q + 4);
-            const float f2 = lane_bperm(nv, 16 * q + 8), f3 = lane_bperm(nv, 16 * q + 12);
-            const float x0 = f0 + (pm[slot][0] + rl[slot][0]), x1 = f1 + (pm[slot][1] + rl[slot][1]);
-            const float x2 = f2 + (pm[slot][2] + rl[slot][2]), x3 = f3 + (pm[slot][3] + rl[slot][3]);
-            const float mx = xor_max<1, 4>(fmaxf(fmaxf(x0, x1), fmaxf(x2, x3)));
-            const float mf = finite_or_zero(mx);
-            const float s = xor_sum<1, 4>((ex2(x0 - mf) + ex2(x1 - mf)) + (ex2(x2 - mf) + ex2(x3 - mf)));
-            const float r = mx + lg2(s);
+        walk<PF>(c0, c1, +1, load, [&](int c, int slot) {
+            float x[CPL];
+#pragma unroll
+            for (int jj = 0; jj < CPL; ++jj) x[jj] = lane_bperm(nv, LPRow * (CPL * q + jj)) + (pm[slot][jj] + rl[slot][jj]);
+            const float r = lse(x);
             O += bs[slot] + (double)dprev;
             nv = r - dprev;
-            dprev = finite_or_zero(xor_max<4, 64>(nv));  // used by the next step
+            dprev = finite_or_zero(xor_max<LPRow, 64>(nv));  // used by the next step
             if (q == 0 && o < T) a.Fv[(cb + c) * T + o] = nv;
             if (lane == 0) a.OF[cb + c] = O;
         });
         if (!grouped && (a.logZ || a.logZ64)) {
-            // entry t sits in lanes 4t .. 4t+3: count it once
-            const float S = xor_sum<1, 64>(q == 0 ? ex2(nv - dprev) : 0.f);
-            const double lz = (O + (double)dprev + (double)lg2(S)) * kLn2;
+            // entry t sits in LPRow lanes: count it once
+            const float Ssum = xor_sum<1, 64>(q == 0 ? ex2(nv - dprev) : 0.f);
+            const double lz = (O + (double)dprev + (double)lg2(Ssum)) * kLn2;
             if (lane == 0 && a.logZ) a.logZ[b] = (float)lz;
             if (lane == 0 && a.logZ64) a.logZ64[b] = lz;
         }
     } else {
-        float nv;  // beta at the last position of chunk c1, entry o in lanes 4o .. 4o+3
+        float nv;  // beta at the last position of chunk c1, entry o in lanes LPRow o ..
         if (c1 == Cb - 1) {
             nv = (o < T) ? 0.f : LCCRF_NEG_INF;
         } else {
@@ -424,27 +535,24 @@ __global__ __launch_bounds__(64) void chunk_boundary_kernel(ScanArgs a) {
             O = a.OGin[bg + g];
         }
         float dprev = 0.f;
-        float pm[kScanPF][4], rl[kScanPF];
-        double bs[kScanPF];
+        float pm[PF][CPL], rl[PF];
+        double bs[PF];
         auto load = [&](int c, int slot) {
-            const float* P = a.Pl + (cb + c) * 256;
+            const float* P = a.Pl + (cb + c) * TP * TP;
 #pragma unroll
-            for (int jj = 0; jj < 4; ++jj) pm[slot][jj] = P[(4 * q + jj) * 16 + o];
-            rl[slot] = a.rel[(cb + c) * 16 + o];
+            for (int jj = 0; jj < CPL; ++jj) pm[slot][jj] = P[(CPL * q + jj) * TP + o];
+            rl[slot] = a.rel[(cb + c) * TP + o];
             bs[slot] = a.base[cb + c];
         };
         // chunk c takes beta at its last position to beta at the last position of chunk c - 1
-        walk<kScanPF>(c1, c0 > 1 ? c0 : 1, -1, load, [&](int c, int slot) {
-            const float g0 = lane_bperm(nv, 16 * q), g1 = lane_bperm(nv, 16 * q + 4);
-            const float g2 = lane_bperm(nv, 16 * q + 8), g3 = lane_bperm(nv, 16 * q + 12);
-            const float x0 = pm[slot][0] + g0, x1 = pm[slot][1] + g1, x2 = pm[slot][2] + g2, x3 = pm[slot][3] + g3;
-            const float mx = xor_max<1, 4>(fmaxf(fmaxf(x0, x1), fmaxf(x2, x3)));
-            const float mf = finite_or_zero(mx);
-            const float s = xor_sum<1, 4>((ex2(x0 - mf) + ex2(x1 - mf)) + (ex2(x2 - mf) + ex2(x3 - mf)));
-            const float r = mx + lg2(s) + rl[slot];
+        walk<PF>(c1, c0 > 1 ? c0 : 1, -1, load, [&](int c, int slot) {
+            float x[CPL];
+#pragma unroll
+            for (int jj = 0; jj < CPL; ++jj) x[jj] = pm[slot][jj] + lane_bperm(nv, LPRow * (CPL * q + jj));
+            const float r = lse(x) + rl[slot];
             O += bs[slot] + (double)dprev;
             nv = r - dprev;
-            dprev = finite_or_zero(xor_max<4, 64>(nv));
+            dprev = finite_or_zero(xor_max<LPRow, 64>(nv));
             if (q == 0 && o < T) a.Gv[(cb + c - 1) * T + o] = nv;
             if (lane == 0) a.OG[cb + c - 1] = O;
         });
@@ -673,7 +781,10 @@ __global__ __launch_bounds__(64) void chunk_maxplus_boundary_kernel(MaxScanArgs 
 }
 
 // ---------------------------------------------------------------------------------------
-bool scan_supported(int T) { return T >= 1 && T <= 16; }
+// Sum queries: tag sets up to 32 (matrices in one or four 16 x 16 blocks); the max-plus scan: up to 16.
+bool scan_supported(int T) { return T >= 1 && T <= 32; }
+bool scan_supported_max(int T) { return T >= 1 && T <= 16; }
+int scan_padded_tags(int T) { return T <= 16 ? 16 : 32; }
 
 // Chunks per group when phase B is itself run as a scan; 0: one serial pass over all chunks.  The
 // group products cost about 3.5 times a vector step each and two serial stages follow them
@@ -685,33 +796,33 @@ int scan_group_size(int C) {
     return gs;
 }
 
-template <typename TIN>
+template <typename TIN, int TP>
 static hipError_t launch_scan_boundaries_t(ScanArgs a, const ScanGroupBuffers& gb, hipStream_t st) {
-    hipLaunchKernelGGL(chunk_product_kernel<TIN>, dim3(a.B * a.C), dim3(64), 0, st, a);
+    hipLaunchKernelGGL((chunk_product_kernel<TIN, TP>), dim3(a.B * a.C), dim3(64), 0, st, a);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     const int gs = scan_group_size(a.C);
     if (gs == 0) {
-        hipLaunchKernelGGL(chunk_boundary_kernel<TIN>, dim3(2 * a.B), dim3(64), 0, st, a);
+        hipLaunchKernelGGL((chunk_boundary_kernel<TIN, TP>), dim3(2 * a.B), dim3(64), 0, st, a);
         return hipGetLastError();
     }
     const int G = (a.C + gs - 1) / gs;
     // products of the groups
     ScanArgs p = a;
     p.GS = gs; p.G = G; p.Pl2 = gb.Pl2; p.rel2 = gb.rel2; p.base2 = gb.base2;
-    hipLaunchKernelGGL(group_product_kernel, dim3(a.B * G), dim3(64), 0, st, p);
+    hipLaunchKernelGGL(group_product_kernel<TP>, dim3(a.B * G), dim3(64), 0, st, p);
     if ((e = hipGetLastError()) != hipSuccess) return e;
     // phase B over the groups: the same kernel, a group in the place of a chunk (this launch writes logZ)
     ScanArgs u = a;
     u.chunk = a.chunk * gs; u.C = G;
     u.Pl = gb.Pl2; u.rel = gb.rel2; u.base = gb.base2; u.Fv = gb.Fv2; u.OF = gb.OF2; u.Gv = gb.Gv2; u.OG = gb.OG2;
-    hipLaunchKernelGGL(chunk_boundary_kernel<TIN>, dim3(2 * a.B), dim3(64), 0, st, u);
+    hipLaunchKernelGGL((chunk_boundary_kernel<TIN, TP>), dim3(2 * a.B), dim3(64), 0, st, u);
     if ((e = hipGetLastError()) != hipSuccess) return e;
     // ... and over the chunks of every group at once
     ScanArgs l = a;
     l.GS = gs; l.G = G; l.logZ = nullptr; l.logZ64 = nullptr;
     l.Fin = gb.Fv2; l.OFin = gb.OF2; l.Gin = gb.Gv2; l.OGin = gb.OG2;
-    hipLaunchKernelGGL(chunk_boundary_kernel<TIN>, dim3(2 * a.B * G), dim3(64), 0, st, l);
+    hipLaunchKernelGGL((chunk_boundary_kernel<TIN, TP>), dim3(2 * a.B * G), dim3(64), 0, st, l);
     return hipGetLastError();
 }
 
@@ -722,7 +833,9 @@ hipError_t launch_scan_boundaries(int dtype, const void* phi, const int32_t* len
     const int C = (N + chunk - 1) / chunk;
     ScanArgs a{phi, lengths, B, N, T, chunk, C, Pl, rel, base, Fv, OF, Gv, OG, logZ, with_beta ? 1 : 0, logZ64,
                0, 1, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr};
-    return dtype == 0 ? launch_scan_boundaries_t<float>(a, gb, st) : launch_scan_boundaries_t<uint16_t>(a, gb, st);
+    if (T <= 16)
+        return dtype == 0 ? launch_scan_boundaries_t<float, 16>(a, gb, st) : launch_scan_boundaries_t<uint16_t, 16>(a, gb, st);
+    return dtype == 0 ? launch_scan_boundaries_t<float, 32>(a, gb, st) : launch_scan_boundaries_t<uint16_t, 32>(a, gb, st);
 }
 
 

@@ -127,10 +127,67 @@ def test_scan_repeat_runs_are_bit_identical(crf):
     assert torch.equal(lz_a, lz_b) and torch.equal(mu_a, mu_b)
 
 
+SUMS = ("logz", "mu")   # the scan of the max-plus semiring stops at 16 tags
+
+
+@pytest.mark.parametrize("k", [4, 7, 32])
+@pytest.mark.parametrize("T,N", [(17, 9), (20, 65), (24, 1), (31, 130), (32, 3), (32, 64), (32, 300)])
+def test_scan_up_to_32_tags(crf, oracle_mod, chunk, T, N, k):
+    """Tag sets of 17 .. 32: chunk products in four 16 x 16 blocks."""
+    chunk(k)
+    lens = _lens_around_chunks(N, k)
+    phi, _ = workloads.random_case(5900 + 31 * T + N, len(lens), N, T, scale=1.5)
+    check_case(crf, oracle_mod, phi, lens, algo=crf.ALGO_SCAN, what=f"scan T={T} N={N} k={k}", queries=SUMS)
+
+
+def test_scan_32_tags_bf16_forbidden_edges_jumps_and_offsets(crf, oracle_mod, chunk):
+    chunk(16)
+    T, N = 32, 200
+    phi, lens = workloads.random_case(5910, 5, N, T, scale=3.0, ragged=True, min_len=3, dtype="bf16")
+    check_case(crf, oracle_mod, phi, lens, poison=False, algo=crf.ALGO_SCAN, what="scan T=32 bf16", queries=SUMS)
+    chunk(8)
+    T, N = 29, 50
+    phi, _ = workloads.random_case(5920, 5, N, T)
+    ninf = float("-inf")
+    phi[0, :, 3, :] = ninf
+    phi[1, 20, :, 27] = ninf
+    phi[2, 30, :, :] = ninf
+    mask = torch.rand(N, T, T, generator=torch.Generator().manual_seed(5)) < 0.6
+    phi[3][mask] = ninf
+    phi[3, :, torch.arange(T), torch.arange(T)] = 0.0
+    lens = torch.tensor([50, 50, 50, 50, 33], dtype=torch.int32)
+    check_case(crf, oracle_mod, phi, lens, poison=False, algo=crf.ALGO_SCAN, what="scan T=29 -inf", queries=SUMS)
+    T, N = 32, 70
+    phi, lens = workloads.random_case(5930, 4, N, T, scale=1.0, ragged=True, min_len=N // 2)
+    g = torch.Generator().manual_seed(17)
+    jump = (torch.randint(0, 3, (4, N, 1, 1), generator=g).to(torch.float32) - 1.0) * 300.0
+    wide = torch.randint(0, 2, (4, N, T, T), generator=g).to(torch.float32) * -150.0
+    wide[:, ::3] = 0.0
+    check_case(crf, oracle_mod, (phi + jump + wide).contiguous(), lens, algo=crf.ALGO_SCAN, what="scan T=32 jumps",
+               queries=SUMS)
+    chunk(16)
+    phi, lens = workloads.random_case(5940, 3, 120, 24, scale=1.0, ragged=True, min_len=60)
+    check_case(crf, oracle_mod, (phi + 40.0).contiguous(), lens, algo=crf.ALGO_SCAN, what="scan T=24 offsets", queries=SUMS)
+
+
+def test_scan_32_tags_agrees_with_sequential_on_the_paper_shape(crf):
+    w = workloads.WORKLOADS["paper_lccrf"]
+    dphi = workloads.phi_batch(w).cuda()
+    lz_a, mu_a = crf.lccrf_marginals(dphi, None, algo=crf.ALGO_SCAN)
+    lz_b, mu_b = crf.lccrf_marginals(dphi, None, algo=crf.ALGO_SEQUENTIAL)
+    lz_c = crf.lccrf_log_partition(dphi, None, algo=crf.ALGO_SCAN)
+    assert torch.allclose(lz_a, lz_b, rtol=2e-6, atol=0)
+    assert torch.allclose(lz_c, lz_b, rtol=2e-6, atol=0)
+    assert float((mu_a - mu_b).abs().max()) < 5e-6
+
+
 def test_scan_needs_a_small_tag_set(crf):
-    phi, _ = workloads.random_case(5800, 2, 8, 17)
+    phi, _ = workloads.random_case(5800, 2, 8, 33)
     with pytest.raises(crf.LccrfError, match="not available"):
         crf.lccrf_marginals(phi.cuda(), None, algo=crf.ALGO_SCAN)
+    phi, _ = workloads.random_case(5801, 2, 8, 17)
+    with pytest.raises(crf.LccrfError, match="not available"):
+        crf.lccrf_argmax(phi.cuda(), None, algo=crf.ALGO_SCAN)
     with pytest.raises(crf.LccrfError, match="invalid argument"):
         crf.set_scan_chunk(3)
 
