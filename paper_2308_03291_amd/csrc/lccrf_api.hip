@@ -14,7 +14,7 @@ int g_scan_chunk = kDefaultScanChunk;
 
 struct SumWorkspace {
     size_t ua, ub, Oa, Ob, mail, failed;
-    size_t Pl, rel, base, Fv, OF, Gv, OG;  // chunked scan (T <= 16 only, else empty)
+    size_t Pl, rel, base, Fv, OF, Gv, OG;  // chunked scan (T <= 32 only, else empty)
     size_t Pl2, rel2, base2, Fv2, OF2, Gv2, OG2;  // its group level (many chunks only, else empty)
     size_t lz64, ha, hb, hoff;             // log-probability, entropy and cross-entropy queries
     size_t total;

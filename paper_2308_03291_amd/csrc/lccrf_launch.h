@@ -35,8 +35,8 @@ hipError_t launch_pair_marginals(int dtype, const void* phi, const int32_t* leng
                                  const float* ua, const float* ub, const double* Oa, const double* Ob,
                                  float* logZ, float* mu, unsigned long long* mail, int* failed, hipStream_t st);
 
-// Chunked scan over positions (lccrf_scan.hip), tag sets of at most 16.  Writes, per chunk of `chunk`
-// positions (C = ceil(N / chunk) chunks per sequence), the chunk's transfer matrix (Pl: 256 floats, rel: 16
+// Chunked scan over positions (lccrf_scan.hip), tag sets of at most 32 (TP = 16 or 32 padded tags).  Writes, per chunk of `chunk`
+// positions (C = ceil(N / chunk) chunks per sequence), the chunk's transfer matrix (Pl: TP^2 floats, rel: TP
 // floats, base: 1 double) and alpha / beta at the chunk's last position (Fv, Gv: T floats; OF, OG: 1
 // double), and logZ if non-null.  with_beta false: forward vectors and logZ only.
 // With many chunks the serial pass over chunks is itself split into groups of scan_group_size(C) chunks

@@ -1,4 +1,5 @@
-// Chunked log-semiring scan over the positions of long chains with a small tag set (T <= 16).
+// Chunked log-semiring scan over the positions of long chains with a small tag set (T <= 32; the
+// max-plus variant T <= 16).
 //
 // The paper (section "Sequence Tagging") notes that the forward algorithm can also be run as a
 // parallel scan over products of T x T matrices, at T times the arithmetic of the sequential
