@@ -25,7 +25,7 @@ def _check(crf, oracle_mod, phi, lens, what):
 # K = 1, K > N, row counts that leave ragged last batches
 SHAPES = [(1, 1, 5), (1, 4, 9), (2, 3, 7), (3, 2, 1), (5, 3, 12), (7, 9, 20), (16, 8, 33), (16, 40, 45), (17, 2, 9),
           (20, 5, 30), (32, 8, 64), (32, 1, 20), (33, 3, 10), (48, 6, 25), (64, 4, 18), (65, 2, 7), (100, 3, 9),
-          (128, 2, 12), (128, 9, 11), (130, 2, 5), (200, 3, 6), (256, 2, 5), (4, 300, 310)]
+          (128, 2, 12), (128, 9, 11), (130, 2, 5), (200, 3, 6), (256, 2, 5), (4, 300, 310), (32, 430, 3)]
 
 
 @pytest.mark.parametrize("T,K,N", SHAPES)
