@@ -17,6 +17,7 @@ struct SumWorkspace {
     size_t Pl, rel, base, Fv, OF, Gv, OG;  // chunked scan (T <= 32 only, else empty)
     size_t Pl2, rel2, base2, Fv2, OF2, Gv2, OG2;  // its group level (many chunks only, else empty)
     size_t lz64, ha, hb, hoff;             // log-probability, entropy and cross-entropy queries
+    size_t ent, lzf;                       // entropy under the scan: per-chunk sums, logZ as float
     size_t total;
 };
 inline SumWorkspace sum_workspace(size_t B, size_t N, size_t T) {
@@ -51,6 +52,8 @@ inline SumWorkspace sum_workspace(size_t B, size_t N, size_t T) {
     w.ha = off; off += round_up(B * T * sizeof(float));
     w.hb = off; off += round_up(B * T * sizeof(float));
     w.hoff = off; off += round_up(B * 2 * sizeof(double));
+    w.ent = off; off += round_up(BC * 2 * sizeof(float));
+    w.lzf = off; off += round_up(B * sizeof(float));
     w.total = off;
     return w;
 }
@@ -291,6 +294,32 @@ int lccrf_entropy(const void* phi, lccrf_dtype dt, const int32_t* lengths, int B
     if (!aligned_to(entropy, 4) || (lengths && !aligned_to(lengths, 4))) return LCCRF_EALIGN;
     const SumWorkspace w = sum_workspace(B, N, T);
     char* base = static_cast<char*>(workspace);
+    // (two passes under the scan against one sequential pass: with 17 .. 32 tags it takes chains twice as long to pay)
+    if (scan_pays(B, N, T) || (scan_pays_sum(B, N, T) && N >= 16 * g_scan_chunk)) {
+        // Under the chunked scan a chain cannot carry its conditional entropy across chunks; the second pass
+        // adds up the entropy edge by edge instead, H = H(y_0) + sum_i H(y_i | y_{i-1}), from the marginals
+        // it forms in registers.
+        hipStream_t st = static_cast<hipStream_t>(stream);
+        float* Fv = reinterpret_cast<float*>(base + w.Fv);
+        double* OF = reinterpret_cast<double*>(base + w.OF);
+        float* Gv = reinterpret_cast<float*>(base + w.Gv);
+        double* OG = reinterpret_cast<double*>(base + w.OG);
+        float* ent = reinterpret_cast<float*>(base + w.ent);
+        float* lzf = reinterpret_cast<float*>(base + w.lzf);
+        hipError_t e = lccrf::launch_scan_boundaries(dt, phi, lengths, B, N, T, g_scan_chunk,
+                                                     reinterpret_cast<float*>(base + w.Pl),
+                                                     reinterpret_cast<float*>(base + w.rel),
+                                                     reinterpret_cast<double*>(base + w.base), Fv, OF, Gv, OG,
+                                                     group_buffers(w, base), lzf, true, st);
+        if (e == hipSuccess)
+            e = lccrf::launch_chunked_marginals(dt, phi, lengths, B, N, T, reinterpret_cast<float*>(base + w.ua),
+                                                reinterpret_cast<float*>(base + w.ub),
+                                                reinterpret_cast<double*>(base + w.Oa),
+                                                reinterpret_cast<double*>(base + w.Ob), nullptr, g_scan_chunk, Fv, OF,
+                                                Gv, OG, st, nullptr, false, ent);
+        if (e == hipSuccess) e = lccrf::launch_entropy_reduce(ent, lengths, lzf, B, N, g_scan_chunk, entropy, st);
+        return e == hipSuccess ? LCCRF_OK : LCCRF_ELAUNCH;
+    }
     const hipError_t e = lccrf::launch_entropy(
         dt, phi, lengths, B, N, T, reinterpret_cast<float*>(base + w.ua), reinterpret_cast<float*>(base + w.ub),
         reinterpret_cast<double*>(base + w.Oa), reinterpret_cast<double*>(base + w.Ob),

@@ -40,6 +40,9 @@ struct ChainArgs {
     // the score under psi (of the score difference) instead, natural units, each less a common offset.
     const void* psi;  // potentials of the second chain, same layout and type as phi
     double* hoff;     // [B][2] the offsets of ha and hb
+    // Entropy by edges (ent non-null, second pass of the one-wave kernels): no marginals are written, every
+    // wave leaves the summed conditional entropies of its edges (base 2) in ent[2 (b C + c) + dir].
+    float* ent;
     // Structured potentials (emit non-null; float only, T <= 64, whole sequences): phi is not read,
     // phi[b][i][s][t] = trans[s][t] + emit[b][i][t].
     const float* emit;   // [B][N][T]

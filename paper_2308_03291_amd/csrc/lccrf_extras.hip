@@ -384,6 +384,34 @@ hipError_t launch_entropy(int dtype, const void* phi, const int32_t* lengths, in
     return launch_entropy_combine(a, H, st);
 }
 
+// Entropy from the per-wave sums of conditional edge entropies the second pass leaves in entropy
+// mode (chunked schedule): H = ln 2 * sum over the chunks of the sequence, both directions.  One
+// wave per sequence.  logZ: what the run has found for log Z ([B] floats): -inf means no finite
+// path, the entropy is NaN then.
+__global__ __launch_bounds__(64) void entropy_reduce_kernel(const float* __restrict__ ent, const int32_t* __restrict__ lengths,
+                                                            const float* __restrict__ logZ, int N, int chunk, int C,
+                                                            float* __restrict__ H) {
+    const int b = blockIdx.x, lane = threadIdx.x;
+    const int L = clamp_length(lengths, b, N);
+    if (L == 0) {
+        if (lane == 0) H[b] = 0.f;
+        return;
+    }
+    const int Cb = (L + chunk - 1) / chunk;
+    double acc = 0.0;
+    for (int k = lane; k < 2 * Cb; k += 64) acc += (double)ent[2 * (size_t)b * C + k];
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) acc += __shfl_xor(acc, off, 64);
+    if (lane == 0) H[b] = logZ[b] == LCCRF_NEG_INF ? __builtin_nanf("") : (float)(acc * kLn2);
+}
+
+hipError_t launch_entropy_reduce(const float* ent, const int32_t* lengths, const float* logZ, int B, int N, int chunk,
+                                 float* H, hipStream_t st) {
+    const int C = (N + chunk - 1) / chunk;
+    hipLaunchKernelGGL(entropy_reduce_kernel, dim3(B), dim3(64), 0, st, ent, lengths, logZ, N, chunk, C, H);
+    return hipGetLastError();
+}
+
 // Cross-entropy H(p, q) = log Z_q - E_p[score_q(y)] (kl = false) or Kullback-Leibler divergence
 // KL(p || q) = E_p[score_p(y) - score_q(y)] - log Z_p + log Z_q (kl = true) of two chains over the
 // same sequences: the expectation from the half chains of p at their meeting position (as the

@@ -102,33 +102,50 @@ __device__ __forceinline__ float max4(const float (&x)[4]) { return fmaxf(fmaxf(
 // computed as U(t) / S(t) + log2 S(t) with U(t) = sum_s e(s,t) [h(s) - log2 e(s,t)] for the same
 // shifted exponentials e the step already forms (hin in row form, hout in column form).
 
-template <int TP, bool WITH_MU, bool ALIGNED, bool WITH_H = false>
+// With ENT (and WITH_MU) the marginals mu_i(s,t) are not stored: the step adds the conditional entropy
+// of the edge, H(y_i | y_{i-1}) = sum_s m(s) log2 m(s) - sum_{s,t} mu log2 mu with m(s) = sum_t mu_i(s,t)
+// (base 2, every term in the lane that holds it; the caller sums hacc over the wave at the end).
+template <int TP, bool WITH_MU, bool ALIGNED, bool WITH_H = false, bool ENT = false>
 __device__ __forceinline__ void wave_fwd_step(float (&v)[WGeo<TP>::R][4], const float (&ua)[WGeo<TP>::R], float c,
                                               const float (&ubK)[4], float* __restrict__ mu_out, int T, int lane,
                                               bool exact_only, float (&r)[4], float& tot,
-                                              const float (&hin)[WGeo<TP>::R], float (&hout)[4]) {
+                                              const float (&hin)[WGeo<TP>::R], float (&hout)[4], float& hacc) {
     using W = WGeo<TP>;
     constexpr int R = W::R;
     const int c4 = 4 * (lane % W::CG), s0 = R * (lane / W::CG);
     bool accepted = false;
     if (!exact_only) {
         float ls[4] = {0.f, 0.f, 0.f, 0.f}, gm[4] = {0.f, 0.f, 0.f, 0.f}, lu[4] = {0.f, 0.f, 0.f, 0.f};
+        float lgm[4] = {0.f, 0.f, 0.f, 0.f}, hstep = 0.f;
         if (WITH_MU) {
 #pragma unroll
-            for (int j = 0; j < 4; ++j) gm[j] = ex2(c + ubK[j]);
+            for (int j = 0; j < 4; ++j) {
+                lgm[j] = c + ubK[j];
+                gm[j] = ex2(lgm[j]);
+            }
         }
 #pragma unroll
         for (int k = 0; k < R; ++k) {
             const float uac = ua[k] - c;
-            float e[4];
+            float e[4], rowl = 0.f;
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
                 const float arg = __builtin_fmaf(v[k][j], kLog2e, uac);
                 e[j] = ex2(arg);
                 ls[j] += e[j];
                 if (WITH_H) lu[j] = __builtin_fmaf(e[j], hin[k] - log2_term(arg), lu[j]);
+                if (ENT) {
+                    const float w = e[j] * gm[j];
+                    rowl += w;
+                    hstep -= w > 0.f ? w * (arg + lgm[j]) : 0.f;
+                }
             }
-            if (WITH_MU) store4<ALIGNED>(mu_out, T, s0 + k, c4, e[0] * gm[0], e[1] * gm[1], e[2] * gm[2], e[3] * gm[3]);
+            if (ENT) {
+                const float m = xor_sum<1, W::CG>(rowl);
+                hstep += (c4 == 0 && m > 0.f) ? m * lg2(m) : 0.f;
+            } else if (WITH_MU) {
+                store4<ALIGNED>(mu_out, T, s0 + k, c4, e[0] * gm[0], e[1] * gm[1], e[2] * gm[2], e[3] * gm[3]);
+            }
         }
         const float part = (ls[0] * gm[0] + ls[1] * gm[1]) + (ls[2] * gm[2] + ls[3] * gm[3]);
         bool ok = true;
@@ -142,6 +159,7 @@ __device__ __forceinline__ void wave_fwd_step(float (&v)[WGeo<TP>::R][4], const 
         }
         accepted = __builtin_amdgcn_ballot_w64(!ok) == 0;
         if (WITH_MU && accepted) tot = xor_sum<1, 64>(part);
+        if (ENT && accepted) hacc += hstep;
     }
     if (!accepted) {
         float lm[4] = {LCCRF_NEG_INF, LCCRF_NEG_INF, LCCRF_NEG_INF, LCCRF_NEG_INF};
@@ -153,23 +171,37 @@ __device__ __forceinline__ void wave_fwd_step(float (&v)[WGeo<TP>::R][4], const 
                 lm[j] = fmaxf(lm[j], v[k][j]);
             }
         float M[4], g[4], ls[4] = {0.f, 0.f, 0.f, 0.f}, gm[4] = {0.f, 0.f, 0.f, 0.f}, lu[4] = {0.f, 0.f, 0.f, 0.f};
+        float lgm[4] = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             M[j] = xor_max<W::CG, 64>(lm[j]);
             g[j] = finite_or_zero(M[j]);
-            if (WITH_MU) gm[j] = ex2(g[j] + ubK[j]);
+            if (WITH_MU) {
+                lgm[j] = g[j] + ubK[j];
+                gm[j] = ex2(lgm[j]);
+            }
         }
 #pragma unroll
         for (int k = 0; k < R; ++k) {
-            float e[4];
+            float e[4], rowl = 0.f;
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
                 const float arg = v[k][j] - g[j];
                 e[j] = ex2(arg);
                 ls[j] += e[j];
                 if (WITH_H) lu[j] = __builtin_fmaf(e[j], hin[k] - log2_term(arg), lu[j]);
+                if (ENT) {
+                    const float w = e[j] * gm[j];
+                    rowl += w;
+                    hacc -= w > 0.f ? w * (arg + lgm[j]) : 0.f;
+                }
             }
-            if (WITH_MU) store4<ALIGNED>(mu_out, T, s0 + k, c4, e[0] * gm[0], e[1] * gm[1], e[2] * gm[2], e[3] * gm[3]);
+            if (ENT) {
+                const float m = xor_sum<1, W::CG>(rowl);
+                hacc += (c4 == 0 && m > 0.f) ? m * lg2(m) : 0.f;
+            } else if (WITH_MU) {
+                store4<ALIGNED>(mu_out, T, s0 + k, c4, e[0] * gm[0], e[1] * gm[1], e[2] * gm[2], e[3] * gm[3]);
+            }
         }
         if (WITH_MU) tot = xor_sum<1, 64>((ls[0] * gm[0] + ls[1] * gm[1]) + (ls[2] * gm[2] + ls[3] * gm[3]));
 #pragma unroll
@@ -183,35 +215,38 @@ __device__ __forceinline__ void wave_fwd_step(float (&v)[WGeo<TP>::R][4], const 
 
 // One backward position: r(s) = log2 sum_t 2^(phi2(s,t) + ub(t)), ub in column form, r in row form.
 // WITH_H: the conditional entropy of the path ahead of the current tag (hin in column form, hout in row form).
-template <int TP, bool WITH_MU, bool ALIGNED, bool WITH_H = false>
+// ENT as in wave_fwd_step; here m(s) = S(s) f(s) and the factor f(s) of row s drops out of log2 (mu / m).
+template <int TP, bool WITH_MU, bool ALIGNED, bool WITH_H = false, bool ENT = false>
 __device__ __forceinline__ void wave_bwd_step(float (&v)[WGeo<TP>::R][4], const float (&ub)[4], float c,
                                               const float (&uaK)[WGeo<TP>::R], float* __restrict__ mu_out, int T,
                                               int lane, bool exact_only, float (&r)[WGeo<TP>::R], float& tot,
-                                              const float (&hin)[4], float (&hout)[WGeo<TP>::R]) {
+                                              const float (&hin)[4], float (&hout)[WGeo<TP>::R], float& hacc) {
     using W = WGeo<TP>;
     constexpr int R = W::R;
     const int c4 = 4 * (lane % W::CG), s0 = R * (lane / W::CG);
     bool accepted = false;
     if (!exact_only) {
         const float ubc[4] = {ub[0] - c, ub[1] - c, ub[2] - c, ub[3] - c};
-        float part = 0.f;
+        float part = 0.f, hstep = 0.f;
         bool ok = true;
 #pragma unroll
         for (int k = 0; k < R; ++k) {
-            float e[4], Ul = 0.f;
+            float e[4], Ul = 0.f, El = 0.f;
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
                 const float arg = __builtin_fmaf(v[k][j], kLog2e, ubc[j]);
                 e[j] = ex2(arg);
                 if (WITH_H) Ul = __builtin_fmaf(e[j], hin[j] - log2_term(arg), Ul);
+                if (ENT) El += e[j] > 0.f ? e[j] * arg : 0.f;
             }
             const float Sl = (e[0] + e[1]) + (e[2] + e[3]);
+            const float S = xor_sum<1, W::CG>(Sl);
             if (WITH_MU) {
                 const float f = ex2(c + uaK[k]);
-                store4<ALIGNED>(mu_out, T, s0 + k, c4, e[0] * f, e[1] * f, e[2] * f, e[3] * f);
+                if (ENT) hstep += f > 0.f ? f * (((c4 == 0 && S > 0.f) ? S * lg2(S) : 0.f) - El) : 0.f;
+                else store4<ALIGNED>(mu_out, T, s0 + k, c4, e[0] * f, e[1] * f, e[2] * f, e[3] * f);
                 part += Sl * f;
             }
-            const float S = xor_sum<1, W::CG>(Sl);
             const bool inm = s0 + k < T;
             r[k] = inm ? c + lg2(S) : LCCRF_NEG_INF;
             ok = ok && (!inm || sum_in_range(S));
@@ -219,6 +254,7 @@ __device__ __forceinline__ void wave_bwd_step(float (&v)[WGeo<TP>::R][4], const 
         }
         accepted = __builtin_amdgcn_ballot_w64(!ok) == 0;
         if (WITH_MU && accepted) tot = xor_sum<1, 64>(part);
+        if (ENT && accepted) hacc += hstep;
     }
     if (!accepted) {
         float part = 0.f;
@@ -228,20 +264,22 @@ __device__ __forceinline__ void wave_bwd_step(float (&v)[WGeo<TP>::R][4], const 
             for (int j = 0; j < 4; ++j) v[k][j] = __builtin_fmaf(v[k][j], kLog2e, ub[j]);
             const float m = xor_max<1, W::CG>(max4(v[k]));
             const float g = finite_or_zero(m);
-            float e[4], Ul = 0.f;
+            float e[4], Ul = 0.f, El = 0.f;
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
                 const float arg = v[k][j] - g;
                 e[j] = ex2(arg);
                 if (WITH_H) Ul = __builtin_fmaf(e[j], hin[j] - log2_term(arg), Ul);
+                if (ENT) El += e[j] > 0.f ? e[j] * arg : 0.f;
             }
             const float Sl = (e[0] + e[1]) + (e[2] + e[3]);
+            const float S = xor_sum<1, W::CG>(Sl);
             if (WITH_MU) {
                 const float f = ex2(g + uaK[k]);
-                store4<ALIGNED>(mu_out, T, s0 + k, c4, e[0] * f, e[1] * f, e[2] * f, e[3] * f);
+                if (ENT) hacc += f > 0.f ? f * (((c4 == 0 && S > 0.f) ? S * lg2(S) : 0.f) - El) : 0.f;
+                else store4<ALIGNED>(mu_out, T, s0 + k, c4, e[0] * f, e[1] * f, e[2] * f, e[3] * f);
                 part += Sl * f;
             }
-            const float S = xor_sum<1, W::CG>(Sl);
             r[k] = (s0 + k < T) ? m + lg2(S) : LCCRF_NEG_INF;
             if (WITH_H) hout[k] = (s0 + k < T) ? entropy_of(xor_sum<1, W::CG>(Ul), S) : 0.f;
         }
@@ -322,7 +360,7 @@ __global__ __launch_bounds__(64) void wave_half_kernel(ChainArgs a) {
             float ua[R], hrow[R];
             col_to_row<TP>(vc, ua, lane);
             if (WITH_H) col_to_row<TP>(hc, hrow, lane);
-            wave_fwd_step<TP, false, ALIGNED, WITH_H>(ring[slot], ua, d, none4, nullptr, T, lane, exact_only, vc, tot, hrow, hc);
+            wave_fwd_step<TP, false, ALIGNED, WITH_H>(ring[slot], ua, d, none4, nullptr, T, lane, exact_only, vc, tot, hrow, hc, tot);
         });
         settle(h);
         if (WITH_H && rg == 0) {
@@ -365,7 +403,7 @@ __global__ __launch_bounds__(64) void wave_half_kernel(ChainArgs a) {
             float ub[4], hcol[4];
             row_to_col<TP>(vr, ub, lane);
             if (WITH_H) row_to_col<TP>(hr, hcol, lane);
-            wave_bwd_step<TP, false, ALIGNED, WITH_H>(ring[slot], ub, d, noneR, nullptr, T, lane, exact_only, vr, tot, hcol, hr);
+            wave_bwd_step<TP, false, ALIGNED, WITH_H>(ring[slot], ub, d, noneR, nullptr, T, lane, exact_only, vr, tot, hcol, hr, tot);
         });
         settle(h);
         if (WITH_H && cg == 0) {
@@ -378,7 +416,10 @@ __global__ __launch_bounds__(64) void wave_half_kernel(ChainArgs a) {
 
 // ---------------------------------------------------------------------------------------
 // Pass 2: both chains continue past the meeting point and write the marginals.
-template <int TP, typename TIN, bool ALIGNED, bool STRUCT>
+// ENT: no marginal is written; every wave adds up the conditional entropies H(y_i | y_{i-1}) of its
+// edges (the wave of position 0 also H(y_0)) and leaves the sum, base 2, in a.ent[2 (b C + c) + dir]:
+// by the chain rule their total is the entropy of the sequence.
+template <int TP, typename TIN, bool ALIGNED, bool STRUCT, bool ENT = false>
 __global__ __launch_bounds__(64) void wave_marginal_kernel(ChainArgs a) {
     using W = WGeo<TP>;
     constexpr int R = W::R, PF = wave_ring_depth(TP, true);
@@ -387,10 +428,11 @@ __global__ __launch_bounds__(64) void wave_marginal_kernel(ChainArgs a) {
     const Span sp = make_span(a, blockIdx.x >> 1);
     const int b = sp.b, N = a.N, T = a.T, L = sp.L;
     const size_t TT = (size_t)T * T, vb = (size_t)b * N;
-    float* mub = a.mu + (size_t)b * N * TT;
+    float* mub = ENT ? nullptr : a.mu + (size_t)b * N * TT;
     const bool exact_only = a.exact_only != 0;
+    float hacc = 0.f;
 
-    if (dir == 0) {
+    if (!ENT && dir == 0) {
         // positions past the end carry no edge: their marginals are zero (a chunk clears its own range)
         const int zfrom = a.chunk > 0 ? (sp.c * a.chunk > L ? sp.c * a.chunk : L) : L;
         const int zto = a.chunk > 0 ? ((sp.c + 1) * a.chunk < N ? (sp.c + 1) * a.chunk : N) : N;
@@ -468,7 +510,7 @@ __global__ __launch_bounds__(64) void wave_marginal_kernel(ChainArgs a) {
             float ubK[4];
 #pragma unroll
             for (int j = 0; j < 4; ++j) ubK[j] = (c4 + j < T) ? aux[slot][j] + K : LCCRF_NEG_INF;
-            wave_fwd_step<TP, true, ALIGNED>(ring[slot], ua, d, ubK, mub + (size_t)i * TT, T, lane, exact_only, vc, tot, noh_r, noh_c);
+            wave_fwd_step<TP, true, ALIGNED, false, ENT>(ring[slot], ua, d, ubK, ENT ? nullptr : mub + (size_t)i * TT, T, lane, exact_only, vc, tot, noh_r, noh_c, hacc);
         });
     } else {
         double O = a.Ob[vb + h];
@@ -499,11 +541,18 @@ __global__ __launch_bounds__(64) void wave_marginal_kernel(ChainArgs a) {
             float uaK[R];
 #pragma unroll
             for (int k = 0; k < R; ++k) uaK[k] = (s0 + k < T) ? aux[slot][k] + K : LCCRF_NEG_INF;
-            wave_bwd_step<TP, true, ALIGNED>(ring[slot], ub, d, uaK, mub + (size_t)i * TT, T, lane, exact_only, vr, tot, noh_c, noh_r);
+            wave_bwd_step<TP, true, ALIGNED, false, ENT>(ring[slot], ub, d, uaK, ENT ? nullptr : mub + (size_t)i * TT, T, lane, exact_only, vr, tot, noh_c, noh_r, hacc);
         });
         // position 0: p(y_0 = t) = softmax_t(alpha_0(t) + beta_0(t)) in row 0, zeros elsewhere
-        if (!sp.first) return;
-        for (int k = T + lane; k < (int)TT; k += 64) mub[k] = 0.f;
+        if (!sp.first) {
+            if (ENT) {
+                hacc = xor_sum<1, 64>(hacc);
+                if (lane == 0) a.ent[2 * ((size_t)b * a.C + sp.c) + 1] = hacc;
+            }
+            return;
+        }
+        if (!ENT)
+            for (int k = T + lane; k < (int)TT; k += 64) mub[k] = 0.f;
         float z[R], m = LCCRF_NEG_INF;
 #pragma unroll
         for (int k = 0; k < R; ++k) {
@@ -518,9 +567,17 @@ __global__ __launch_bounds__(64) void wave_marginal_kernel(ChainArgs a) {
         const float cnorm = (feasible && S > 0.f) ? 1.0f / S : 0.f;
         if (cg == 0) {
 #pragma unroll
-            for (int k = 0; k < R; ++k)
-                if (s0 + k < T) mub[s0 + k] = cnorm * ex2(z[k] - m);
+            for (int k = 0; k < R; ++k) {
+                if (s0 + k >= T) continue;
+                const float p = cnorm * ex2(z[k] - m);
+                if (ENT) hacc -= p > 0.f ? p * (z[k] - m - lg2(S)) : 0.f;  // H(y_0)
+                else mub[s0 + k] = p;
+            }
         }
+    }
+    if (ENT) {
+        hacc = xor_sum<1, 64>(hacc);
+        if (lane == 0) a.ent[2 * ((size_t)b * a.C + sp.c) + dir] = hacc;
     }
 }
 
@@ -539,7 +596,9 @@ static hipError_t launch_wave_tp(bool second_pass, const ChainArgs& a, hipStream
             return hipGetLastError();
         }
     }
-    if (second_pass)
+    if (second_pass && a.ent)
+        hipLaunchKernelGGL((wave_marginal_kernel<TP, TIN, ALIGNED, false, true>), grid, dim3(64), 0, st, a);
+    else if (second_pass)
         hipLaunchKernelGGL((wave_marginal_kernel<TP, TIN, ALIGNED, false>), grid, dim3(64), 0, st, a);
     else if (a.ha)
         hipLaunchKernelGGL((wave_half_kernel<TP, TIN, ALIGNED, true, false>), grid, dim3(64), 0, st, a);

@@ -100,6 +100,34 @@ def test_entropy_peaked_bf16_and_forbidden_edges(crf, oracle_mod, T):
     _check_entropy(crf, oracle_mod, phi, None, f"-inf T={T}")
 
 
+@pytest.mark.parametrize("T,N", [(3, 256), (5, 700), (16, 300), (16, 1000), (20, 260), (24, 513), (32, 256), (32, 640)])
+def test_entropy_under_the_scan(crf, oracle_mod, T, N):
+    """Long chains in small batches take the chunked scan: the entropy is then added up edge by edge
+    (H(y_0) + sum_i H(y_i | y_{i-1})) in the second pass, chunk by chunk."""
+    phi, lens = workloads.random_case(6500 + 13 * T + N, 5, N, T, scale=1.5, ragged=True, min_len=0)
+    lens[0] = N
+    lens[1] = 1
+    _check_entropy(crf, oracle_mod, phi, lens, f"scan T={T} N={N}")
+
+
+def test_entropy_under_the_scan_peaked_bf16_and_forbidden_edges(crf, oracle_mod):
+    w = workloads.WORKLOADS["cfg5"]
+    _check_entropy(crf, oracle_mod, workloads.phi_batch(w), workloads.lengths(w), "cfg5")
+    T, N = 16, 400
+    phi, _ = workloads.random_case(6600, 4, N, T)
+    ninf = float("-inf")
+    phi[0, :, 3, :] = ninf
+    phi[1, 210, :, 5] = ninf
+    phi[2, 300, :, :] = ninf          # no finite path: NaN on both sides
+    mask = torch.rand(N, T, T, generator=torch.Generator().manual_seed(7)) < 0.5
+    phi[3][mask] = ninf
+    phi[3, :, torch.arange(T), torch.arange(T)] = 0.0
+    _check_entropy(crf, oracle_mod, phi, None, "scan -inf")
+    H = crf.lccrf_entropy(torch.zeros(3, 512, 32, 32, device="cuda"),
+                          torch.tensor([512, 300, 0], dtype=torch.int32, device="cuda")).cpu().numpy()
+    assert np.allclose(H, np.array([512, 300, 0]) * math.log(32), rtol=1e-5)
+
+
 @pytest.mark.parametrize("key", ["cfg1", "cfg2", "cfg3"])
 def test_entropy_named_workloads(crf, oracle_mod, key):
     w = workloads.WORKLOADS[key]
