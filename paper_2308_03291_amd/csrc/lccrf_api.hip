@@ -18,6 +18,7 @@ struct SumWorkspace {
     size_t Pl2, rel2, base2, Fv2, OF2, Gv2, OG2;  // its group level (many chunks only, else empty)
     size_t lz64, ha, hb, hoff;             // log-probability, entropy and cross-entropy queries
     size_t ent, lzf;                       // entropy under the scan: per-chunk sums, logZ as float
+    size_t maps;                           // sampling: the map of every position, [B][N][T] bytes
     size_t total;
 };
 inline SumWorkspace sum_workspace(size_t B, size_t N, size_t T) {
@@ -54,6 +55,7 @@ inline SumWorkspace sum_workspace(size_t B, size_t N, size_t T) {
     w.hoff = off; off += round_up(B * 2 * sizeof(double));
     w.ent = off; off += round_up(BC * 2 * sizeof(float));
     w.lzf = off; off += round_up(B * sizeof(float));
+    w.maps = off; off += round_up(B * N * T);
     w.total = off;
     return w;
 }
@@ -381,10 +383,25 @@ int lccrf_sample(const void* phi, lccrf_dtype dt, const int32_t* lengths, const 
     char* base = static_cast<char*>(workspace);
     hipStream_t st = static_cast<hipStream_t>(stream);
     float* ua = reinterpret_cast<float*>(base + w.ua);
-    hipError_t e = lccrf::launch_full_forward(dt, phi, lengths, B, N, T, ua, reinterpret_cast<float*>(base + w.ub),
-                                              reinterpret_cast<double*>(base + w.Oa),
-                                              reinterpret_cast<double*>(base + w.Ob), st);
-    if (e == hipSuccess) e = lccrf::launch_backward_sample(dt, phi, lengths, ua, uniforms, B, N, T, tags, st);
+    float* ub = reinterpret_cast<float*>(base + w.ub);
+    double* Oa = reinterpret_cast<double*>(base + w.Oa);
+    double* Ob = reinterpret_cast<double*>(base + w.Ob);
+    hipError_t e;
+    if (scan_pays_sum(B, N, T)) {  // alpha everywhere, chunk by chunk from the scan's boundary vectors
+        float* Fv = reinterpret_cast<float*>(base + w.Fv);
+        double* OF = reinterpret_cast<double*>(base + w.OF);
+        e = lccrf::launch_scan_boundaries(dt, phi, lengths, B, N, T, g_scan_chunk, reinterpret_cast<float*>(base + w.Pl),
+                                          reinterpret_cast<float*>(base + w.rel), reinterpret_cast<double*>(base + w.base),
+                                          Fv, OF, reinterpret_cast<float*>(base + w.Gv),
+                                          reinterpret_cast<double*>(base + w.OG), group_buffers(w, base), nullptr, false, st);
+        if (e == hipSuccess)
+            e = lccrf::launch_chunked_full_forward(dt, phi, lengths, B, N, T, ua, ub, Oa, Ob, g_scan_chunk, Fv, OF, st);
+    } else {
+        e = lccrf::launch_full_forward(dt, phi, lengths, B, N, T, ua, ub, Oa, Ob, st);
+    }
+    if (e == hipSuccess)
+        e = lccrf::launch_backward_sample(dt, phi, lengths, ua, Oa, uniforms, B, N, T,
+                                          reinterpret_cast<uint8_t*>(base + w.maps), tags, st);
     return e == hipSuccess ? LCCRF_OK : LCCRF_ELAUNCH;
 }
 

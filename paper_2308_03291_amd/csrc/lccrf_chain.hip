@@ -917,6 +917,16 @@ hipError_t launch_full_forward(int dtype, const void* phi, const int32_t* length
     return aligned ? launch_T<uint16_t, true>(2, a, st, nullptr, pair) : launch_T<uint16_t, false>(2, a, st, nullptr, pair);
 }
 
+hipError_t launch_chunked_full_forward(int dtype, const void* phi, const int32_t* lengths, int B, int N, int T,
+                                       float* ua, float* ub, double* Oa, double* Ob, int chunk, const float* Fv,
+                                       const double* OF, hipStream_t st) {
+    if (!wave_supported(T)) return hipErrorInvalidValue;
+    const int C = (N + chunk - 1) / chunk;
+    ChainArgs a{phi, lengths, B, N, T, ua, ub, Oa, Ob, nullptr, nullptr, 0, nullptr, chunk, C, Fv, OF, nullptr, nullptr};
+    a.full_forward = 1;
+    return launch_wave(2, dtype, a, st, nullptr);
+}
+
 // op: 0 = logZ only, 1 = marginals (+ logZ).  Workspace pointers already carved by the caller.
 hipError_t launch_sequential_sum(int op, int dtype, const void* phi, const int32_t* lengths, int B, int N, int T,
                                  float* ua, float* ub, double* Oa, double* Ob, float* logZ, float* mu,

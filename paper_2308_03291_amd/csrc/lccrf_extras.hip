@@ -472,103 +472,223 @@ hipError_t launch_cross(bool kl, int dtype, const void* phi_p, const void* phi_q
 // y_{L-1} ~ exp(alpha_{L-1}(t)), then y_i ~ exp(alpha_i(s) + phi_{i+1}(s, y_{i+1})) going down.
 // The randomness is an input: uniforms[b][i] decides position i by inversion of the cumulative
 // weights over ascending tags (the smallest tag whose cumulative weight exceeds u * total; the
-// last tag of positive weight if rounding leaves none).  One wave per sequence; lane l owns the
-// K consecutive tags l K .. l K + K - 1 so that the lane-wise prefix sums keep the tag order.
-template <typename TIN, int K>
-__global__ __launch_bounds__(64) void backward_sample_kernel(const TIN* __restrict__ phi, const int32_t* __restrict__ lengths,
-                                                            const float* __restrict__ ua, const float* __restrict__ uniforms,
-                                                            int N, int T, int32_t* __restrict__ tags) {
+// last tag of positive weight if rounding leaves none).
+//
+// With the uniforms fixed, position i is a MAP from the tag above it to its own tag, and that map
+// does not depend on any other position: F_i[t] = the tag drawn for y_i if y_{i+1} = t.  So the
+// sweep splits into a pass that is parallel over all positions and reads phi once
+// (sample_map_kernel: all T columns of every matrix, T^2 work a position like a forward step) and
+// a walk through the table of maps that touches one byte a position (sample_walk_kernel), instead
+// of N dependent column gathers from HBM.  The total weight of column t is alpha_{i+1}(t), which
+// the forward pass has stored, so one sweep over the rows of a column finds where the running sum
+// crosses u (weights relative to that total; it equals the sum up to the rounding of the forward
+// step, which matters only for a draw closer than that to the edge of a tag's interval).
+
+// LPP lanes serve one position (16, 32 or 64: the tag count rounded up), CPT columns a lane (more
+// than one only above 64 tags); a wave serves 64 / LPP positions, a workgroup four waves.
+template <typename TIN, int LPP, int CPT>
+__global__ __launch_bounds__(256) void sample_map_kernel(const TIN* __restrict__ phi, const int32_t* __restrict__ lengths,
+                                                         const float* __restrict__ ua, const double* __restrict__ Oa,
+                                                         const float* __restrict__ uniforms, int B, int N, int T,
+                                                         uint8_t* __restrict__ F) {
+    constexpr int PPW = 64 / LPP, TCAP = LPP * CPT;
+    __shared__ float alds[4][PPW][TCAP];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int pl = lane / LPP, tl = lane % LPP;
+    const long long unit = ((long long)blockIdx.x * 4 + wave) * PPW + pl;  // (b, i), i = 0 .. N-2
+    if (unit >= (long long)B * (N - 1)) return;
+    const int b = (int)(unit / (N - 1)), i = (int)(unit % (N - 1));
+    const int L = clamp_length(lengths, b, N);
+    if (i >= L - 1) return;
+    const size_t TT = (size_t)T * T, vb = (size_t)b * N;
+    const TIN* mat = phi + (vb + i + 1) * TT;  // phi_{i+1}
+    const float dO = (float)(Oa[vb + i] - Oa[vb + i + 1]);
+    const float u = uniforms[vb + i];
+    float base[CPT], cum[CPT];
+    int first[CPT], last[CPT], col[CPT];
+#pragma unroll
+    for (int c = 0; c < CPT; ++c) {
+        const int t = tl + c * LPP;
+        col[c] = t < T ? t : T - 1;
+        base[c] = t < T ? dO - ua[(vb + i + 1) * T + t] : LCCRF_NEG_INF;  // an unreachable tag above: +inf, no weight
+        if (!(base[c] < __builtin_huge_valf())) base[c] = LCCRF_NEG_INF;
+        alds[wave][pl][t] = t < T ? ua[(vb + i) * T + t] : LCCRF_NEG_INF;
+        cum[c] = 0.f;
+        first[c] = -1;
+        last[c] = -1;
+    }
+    const float* arow = alds[wave][pl];
+#pragma unroll 4
+    for (int s = 0; s < T; ++s) {
+        const float as = arow[s];
+        const TIN* row = mat + (size_t)s * T;
+#pragma unroll
+        for (int c = 0; c < CPT; ++c) {
+            const float w = ex2(__builtin_fmaf(Elem<TIN>::get(row + col[c]), kLog2e, base[c]) + as);
+            cum[c] += w;
+            last[c] = w > 0.f ? s : last[c];
+            first[c] = (first[c] < 0 && cum[c] > u) ? s : first[c];
+        }
+    }
+#pragma unroll
+    for (int c = 0; c < CPT; ++c) {
+        const int t = tl + c * LPP;
+        const int pick = first[c] >= 0 ? first[c] : (last[c] >= 0 ? last[c] : 0);
+        if (t < T) F[(vb + i) * T + t] = (uint8_t)pick;
+    }
+}
+
+constexpr int kWalkWindow = 16384;  // bytes of the table of maps held in LDS at a time
+
+// One wave per sequence: draws y_{L-1} from alpha_{L-1}, then follows the maps down.  K tags a lane
+// (lane l owns tags l K .. l K + K - 1, so that lane-wise prefix sums keep the tag order).
+template <int K>
+__global__ __launch_bounds__(64) void sample_walk_kernel(const int32_t* __restrict__ lengths, const float* __restrict__ ua,
+                                                         const float* __restrict__ uniforms, const uint8_t* __restrict__ F,
+                                                         int N, int T, int32_t* __restrict__ tags) {
+    __shared__ __attribute__((aligned(16))) uint8_t win[kWalkWindow];
+    __shared__ uint8_t segmap[64 * 256];
+    __shared__ uint8_t entry[65];
     const int b = blockIdx.x, lane = threadIdx.x;
     const int L = clamp_length(lengths, b, N);
     int32_t* y = tags + (size_t)b * N;
     for (int i = L + lane; i < N; i += 64) y[i] = -1;
     if (L == 0) return;
-    const size_t TT = (size_t)T * T;
-    const TIN* phib = phi + (size_t)b * N * TT;
-    const float* uab = ua + (size_t)b * N * T;
-    const float* ub = uniforms + (size_t)b * N;
-    int next = 0;
-    bool dead = false;
-    float a_cur[K];
+    const size_t vb = (size_t)b * N;
+    // the last position: inversion over exp(alpha_{L-1})
+    float w[K], m = LCCRF_NEG_INF;
 #pragma unroll
     for (int k = 0; k < K; ++k) {
         const int s = lane * K + k;
-        a_cur[k] = s < T ? uab[(size_t)(L - 1) * T + s] : LCCRF_NEG_INF;
+        w[k] = s < T ? ua[(vb + L - 1) * T + s] : LCCRF_NEG_INF;
+        m = fmaxf(m, w[k]);
     }
-    for (int i = L - 1; i >= 0; --i) {
-        float a_prev[K];  // alpha of the position below, requested before this position's dependent work
-#pragma unroll
-        for (int k = 0; k < K; ++k) {
-            const int s = lane * K + k;
-            a_prev[k] = (i > 0 && s < T) ? uab[(size_t)(i - 1) * T + s] : LCCRF_NEG_INF;
-        }
-        float w[K], m = LCCRF_NEG_INF;
-#pragma unroll
-        for (int k = 0; k < K; ++k) {
-            const int s = lane * K + k;
-            w[k] = a_cur[k];
-            if (i < L - 1 && s < T) w[k] += Elem<TIN>::get(phib + (size_t)(i + 1) * TT + (size_t)s * T + next) * kLog2e;
-            m = fmaxf(m, w[k]);
-        }
-        m = xor_max<1, 64>(m);
-        int pick = 0;
-        if (m == LCCRF_NEG_INF) {
-            dead = true;  // no finite path: all tags 0
-        } else {
-            float part = 0.f;
-#pragma unroll
-            for (int k = 0; k < K; ++k) {
-                w[k] = ex2(w[k] - m);
-                part += w[k];
-            }
-            // inclusive prefix sum over lanes (ascending lane = ascending tag)
-            float incl = part;
-#pragma unroll
-            for (int off = 1; off < 64; off <<= 1) {
-                const float v = __shfl_up(incl, off, 64);
-                if (lane >= off) incl += v;
-            }
-            const float total = __shfl(incl, 63, 64);
-            const float target = ub[i] * total;
-            float cum = incl - part;
-            int first_over = 0x7fffffff, last_pos = -1;
-#pragma unroll
-            for (int k = 0; k < K; ++k) {
-                const int s = lane * K + k;
-                cum += w[k];
-                if (w[k] > 0.f) last_pos = s;
-                if (first_over == 0x7fffffff && cum > target && s < T) first_over = s;
-            }
-#pragma unroll
-            for (int off = 1; off < 64; off <<= 1) {
-                first_over = min(first_over, __shfl_xor(first_over, off, 64));
-                last_pos = max(last_pos, __shfl_xor(last_pos, off, 64));
-            }
-            pick = first_over != 0x7fffffff ? first_over : last_pos;
-        }
-        if (dead) break;
-        if (lane == 0) y[i] = pick;
-        next = pick;
-#pragma unroll
-        for (int k = 0; k < K; ++k) a_cur[k] = a_prev[k];
-    }
-    if (dead)
+    m = xor_max<1, 64>(m);
+    if (m == LCCRF_NEG_INF) {  // no finite path: all tags 0
         for (int i = lane; i < L; i += 64) y[i] = 0;
+        return;
+    }
+    float part = 0.f;
+#pragma unroll
+    for (int k = 0; k < K; ++k) {
+        w[k] = ex2(w[k] - m);
+        part += w[k];
+    }
+    float incl = part;  // inclusive prefix sum over lanes (ascending lane = ascending tag)
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        const float v = __shfl_up(incl, off, 64);
+        if (lane >= off) incl += v;
+    }
+    const float target = uniforms[vb + L - 1] * __shfl(incl, 63, 64);
+    float cum = incl - part;
+    int first_over = 0x7fffffff, last_pos = -1;
+#pragma unroll
+    for (int k = 0; k < K; ++k) {
+        const int s = lane * K + k;
+        cum += w[k];
+        if (w[k] > 0.f) last_pos = s;
+        if (first_over == 0x7fffffff && cum > target && s < T) first_over = s;
+    }
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        first_over = min(first_over, __shfl_xor(first_over, off, 64));
+        last_pos = max(last_pos, __shfl_xor(last_pos, off, 64));
+    }
+    int cur = first_over != 0x7fffffff ? first_over : last_pos;
+    if (lane == 0) y[L - 1] = cur;
+    // Positions L-2 .. 0 through LDS windows of the table.  A short window is walked by one lane.  A
+    // long one (small tag sets) is cut into 64 segments: every lane first composes the maps of its
+    // segment for all T possible tags above it (independent look-ups, so they overlap), one lane
+    // then passes the actual tag down through the 64 segment maps, and every lane walks its segment
+    // from the tag it was handed.
+    const int wp = kWalkWindow / T;  // positions a window (T <= 256: at least 64)
+    int hi = L - 1;                  // positions [0, hi) still to walk
+    while (hi > 0) {
+        const int lo = hi - wp > 0 ? hi - wp : 0;
+        const int np = hi - lo;
+        const uint8_t* src = F + (vb + lo) * T;
+        const int nbytes = np * T;
+        if (((reinterpret_cast<uintptr_t>(src) | (uintptr_t)nbytes) & 15) == 0) {
+            for (int k = lane; k < nbytes / 16; k += 64)
+                reinterpret_cast<uint4*>(win)[k] = reinterpret_cast<const uint4*>(src)[k];
+        } else {
+            for (int k = lane; k < nbytes; k += 64) win[k] = src[k];
+        }
+        __syncthreads();
+        if (np <= 128) {
+            if (lane == 0) {
+                for (int i = hi - 1; i >= lo; --i) {
+                    cur = win[(i - lo) * T + cur];
+                    y[i] = cur;
+                }
+            }
+        } else {
+            const int seg = (np + 63) / 64;
+            const int bot = lane * seg < np ? lane * seg : np, top = bot + seg < np ? bot + seg : np;  // window-relative
+            for (int c0 = 0; c0 < T; c0 += 4) {
+                int t0 = c0, t1 = c0 + 1 < T ? c0 + 1 : c0, t2 = c0 + 2 < T ? c0 + 2 : c0, t3 = c0 + 3 < T ? c0 + 3 : c0;
+                for (int r = top - 1; r >= bot; --r) {
+                    const uint8_t* row = win + r * T;
+                    t0 = row[t0]; t1 = row[t1]; t2 = row[t2]; t3 = row[t3];
+                }
+                segmap[lane * T + c0] = (uint8_t)t0;
+                if (c0 + 1 < T) segmap[lane * T + c0 + 1] = (uint8_t)t1;
+                if (c0 + 2 < T) segmap[lane * T + c0 + 2] = (uint8_t)t2;
+                if (c0 + 3 < T) segmap[lane * T + c0 + 3] = (uint8_t)t3;
+            }
+            __syncthreads();
+            if (lane == 0) {
+                for (int l = 63; l >= 0; --l) {
+                    entry[l] = (uint8_t)cur;
+                    cur = segmap[l * T + cur];
+                }
+                entry[64] = (uint8_t)cur;
+            }
+            __syncthreads();
+            int t = entry[lane];
+            for (int r = top - 1; r >= bot; --r) {
+                t = win[r * T + t];
+                y[lo + r] = t;
+            }
+            cur = entry[64];
+        }
+        __syncthreads();
+        hi = lo;
+    }
 }
 
 template <typename TIN>
-static hipError_t launch_sample_T(const TIN* phi, const int32_t* lengths, const float* ua, const float* uniforms, int B, int N,
-                                  int T, int32_t* tags, hipStream_t st) {
-    if (T <= 64) hipLaunchKernelGGL((backward_sample_kernel<TIN, 1>), dim3(B), dim3(64), 0, st, phi, lengths, ua, uniforms, N, T, tags);
-    else if (T <= 128) hipLaunchKernelGGL((backward_sample_kernel<TIN, 2>), dim3(B), dim3(64), 0, st, phi, lengths, ua, uniforms, N, T, tags);
-    else hipLaunchKernelGGL((backward_sample_kernel<TIN, 4>), dim3(B), dim3(64), 0, st, phi, lengths, ua, uniforms, N, T, tags);
+static hipError_t launch_sample_T(const TIN* phi, const int32_t* lengths, const float* ua, const double* Oa,
+                                  const float* uniforms, int B, int N, int T, uint8_t* F, int32_t* tags, hipStream_t st) {
+    if (N > 1) {
+        const long long units = (long long)B * (N - 1);
+        auto blocks = [&](int ppw) { return dim3((unsigned)((units + 4 * ppw - 1) / (4 * ppw))); };
+        if (T <= 16)
+            hipLaunchKernelGGL((sample_map_kernel<TIN, 16, 1>), blocks(4), dim3(256), 0, st, phi, lengths, ua, Oa, uniforms, B, N, T, F);
+        else if (T <= 32)
+            hipLaunchKernelGGL((sample_map_kernel<TIN, 32, 1>), blocks(2), dim3(256), 0, st, phi, lengths, ua, Oa, uniforms, B, N, T, F);
+        else if (T <= 64)
+            hipLaunchKernelGGL((sample_map_kernel<TIN, 64, 1>), blocks(1), dim3(256), 0, st, phi, lengths, ua, Oa, uniforms, B, N, T, F);
+        else if (T <= 128)
+            hipLaunchKernelGGL((sample_map_kernel<TIN, 64, 2>), blocks(1), dim3(256), 0, st, phi, lengths, ua, Oa, uniforms, B, N, T, F);
+        else
+            hipLaunchKernelGGL((sample_map_kernel<TIN, 64, 4>), blocks(1), dim3(256), 0, st, phi, lengths, ua, Oa, uniforms, B, N, T, F);
+        const hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    if (T <= 64) hipLaunchKernelGGL(sample_walk_kernel<1>, dim3(B), dim3(64), 0, st, lengths, ua, uniforms, F, N, T, tags);
+    else if (T <= 128) hipLaunchKernelGGL(sample_walk_kernel<2>, dim3(B), dim3(64), 0, st, lengths, ua, uniforms, F, N, T, tags);
+    else hipLaunchKernelGGL(sample_walk_kernel<4>, dim3(B), dim3(64), 0, st, lengths, ua, uniforms, F, N, T, tags);
     return hipGetLastError();
 }
 
-hipError_t launch_backward_sample(int dtype, const void* phi, const int32_t* lengths, const float* ua,
-                                  const float* uniforms, int B, int N, int T, int32_t* tags, hipStream_t st) {
-    if (dtype == 0) return launch_sample_T(static_cast<const float*>(phi), lengths, ua, uniforms, B, N, T, tags, st);
-    return launch_sample_T(static_cast<const uint16_t*>(phi), lengths, ua, uniforms, B, N, T, tags, st);
+// ua, Oa: alpha of every position from the forward pass ([B][N][T] normalised vectors, [B][N] offsets);
+// F: [B][N][T] bytes of scratch for the maps.
+hipError_t launch_backward_sample(int dtype, const void* phi, const int32_t* lengths, const float* ua, const double* Oa,
+                                  const float* uniforms, int B, int N, int T, uint8_t* F, int32_t* tags, hipStream_t st) {
+    if (dtype == 0) return launch_sample_T(static_cast<const float*>(phi), lengths, ua, Oa, uniforms, B, N, T, F, tags, st);
+    return launch_sample_T(static_cast<const uint16_t*>(phi), lengths, ua, Oa, uniforms, B, N, T, F, tags, st);
 }
 
 }  // namespace lccrf

@@ -59,6 +59,57 @@ def test_sample_bf16_and_forbidden_edges(crf, oracle_mod):
     assert (got[2] == 0).all() and (got[1, 10] != 5)
 
 
+def _check_every_draw(crf, oracle_mod, phi, lens, seed, what, tol=1e-4):
+    """Long chains: the oracle's closest draw is almost surely within rounding of a boundary somewhere
+    along thousands of positions, after which the two chains condition on different tags.  So every
+    draw of the GPU's path is checked on its own, given the GPU's own tag above it: with the oracle's
+    fp64 alpha, u_i * total must lie in the interval of the chosen tag, up to tol of the total."""
+    B, N, T, _ = phi.shape
+    u = torch.rand(B, N, generator=torch.Generator().manual_seed(seed))
+    got = crf.lccrf_sample(phi.cuda(), u.cuda(), None if lens is None else lens.cuda()).cpu().numpy()
+    lens_np = np.full((B,), N) if lens is None else np.clip(lens.numpy(), 0, N)
+    alpha, _, _ = oracle_mod.forward_backward(phi, lens_np.astype(np.int32))
+    phi64 = phi.to(torch.float32).numpy()
+    un = u.numpy().astype(np.float64)
+    worst = 0.0
+    for b in range(B):
+        L = int(lens_np[b])
+        assert (got[b, L:] == -1).all(), f"{what}: tags past the length of sequence {b}"
+        if L == 0:
+            continue
+        y = got[b, :L].astype(np.int64)
+        assert ((y >= 0) & (y < T)).all()
+        logw = alpha[b, :L].copy()                                   # [L, T] over the candidate tag s
+        logw[:L - 1] += phi64[b, np.arange(1, L), :, y[1:]].astype(np.float64)   # + phi_{i+1}(s, y_{i+1})
+        w = np.exp(logw - logw.max(axis=1, keepdims=True))
+        cum = np.cumsum(w, axis=1)
+        tot = cum[:, -1]
+        target = un[b, :L] * tot
+        upper = cum[np.arange(L), y]
+        lower = upper - w[np.arange(L), y]
+        assert (w[np.arange(L), y] > 0).all(), f"{what}: a tag of weight 0 was drawn in sequence {b}"
+        below = np.maximum(lower - target, 0.0) / tot                # the draw lies below the tag's interval
+        # above the interval is allowed only for the last tag of positive weight (the rounding rule)
+        is_last = np.array([y[i] == np.nonzero(w[i] > 0)[0][-1] for i in range(L)])
+        above = np.where(is_last, 0.0, np.maximum(target - upper, 0.0) / tot)
+        worst = max(worst, float(below.max()), float(above.max()))
+    assert worst <= tol, f"{what}: a draw misses its tag's interval by {worst:.2e} of the total weight"
+
+
+@pytest.mark.parametrize("T,N", [(3, 6000), (5, 700), (16, 3000), (20, 300), (32, 600), (48, 400), (128, 200)])
+def test_sample_long_chains(crf, oracle_mod, T, N):
+    """Several windows of the table of maps, the segmented walk for small tag sets, and (T <= 32) the forward
+    pass under the chunked scan."""
+    phi, lens = workloads.random_case(8400 + 13 * T + N, 4, N, T, scale=1.5, ragged=True, min_len=N // 2)
+    lens[0] = N
+    _check_every_draw(crf, oracle_mod, phi, lens, 200 + T, f"long T={T} N={N}")
+
+
+def test_sample_config5(crf, oracle_mod):
+    w = workloads.WORKLOADS["cfg5"]
+    _check_every_draw(crf, oracle_mod, workloads.phi_batch(w), workloads.lengths(w), 12, "cfg5")
+
+
 def test_sample_frequencies(crf):
     """Many independent draws from one small chain: path frequencies match the probabilities that
     lccrf_log_prob assigns (5 sigma)."""
