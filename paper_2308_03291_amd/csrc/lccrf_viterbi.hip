@@ -326,6 +326,163 @@ __global__ __launch_bounds__(G::W) void viterbi_half_kernel(VitArgs a) {
     if (tid < T) mid[tid] = sm.dvec[buf][tid];
 }
 
+// The first maximum of val[0 .. n-1] (arg ascending with the index) ends in val[0] / arg[0]: a tree
+// of pairwise comparisons in which the right-hand candidate wins only if strictly greater, so the
+// chain of dependent instructions is log2 n long instead of n.
+template <int n>
+__device__ __forceinline__ void first_max_tree(double (&val)[n], int (&arg)[n]) {
+#pragma unroll
+    for (int w = 1; w < n; w <<= 1)
+#pragma unroll
+        for (int k = 0; k + w < n; k += 2 * w)
+            if (val[k + w] > val[k]) { val[k] = val[k + w]; arg[k] = arg[k + w]; }
+}
+
+// One wave per chain for T <= 32 (TP = 16 or 32 padded tags): the whole matrix of a position is spread
+// over the 64 lanes, the vector of the previous position sits in LDS, and nothing but that vector
+// crosses lanes, so a step needs no barrier between waves and no merge through LDS.
+//   forward:  LPC = 64 / TP lanes share a column t (lane = part TP + t), each takes the rows
+//             part RPL .. part RPL + RPL - 1 in ascending order and the LPC partial winners are
+//             merged with lane exchanges (for a fixed row the lanes read consecutive addresses);
+//   backward: LPC lanes share a row s (lane = s LPC + part), each takes RPL consecutive columns
+//             (vector loads), merged in the same way.
+// Same outputs as viterbi_half_kernel: pointers in bp, the two vectors of the meeting point in mid.
+template <int TP, typename TIN, bool ALIGNED, bool STRUCT>
+__global__ __launch_bounds__(64) void viterbi_wave_kernel(VitArgs a) {
+    constexpr int LPC = 64 / TP, RPL = TP / LPC, PF = 3;
+    __shared__ double dvec[2][TP];
+    const int lane = threadIdx.x;
+    const int dir = blockIdx.x & 1;
+    const VitSpan sp = vit_span(a, blockIdx.x >> 1);
+    if (sp.empty) return;
+    const int b = sp.b, N = a.N, T = a.T;
+    const int p0 = sp.p0, e = sp.e, h = meeting_point(p0, e);
+    const size_t TT = (size_t)T * T;
+    const TIN* phib = STRUCT ? nullptr : static_cast<const TIN*>(a.phi) + (size_t)b * N * TT;
+    const float* emb = STRUCT ? a.emit + (size_t)b * N * T : nullptr;
+    uint8_t* bpb = a.bp + (size_t)b * N * T;
+    double* mid = a.mid + (((size_t)b * a.C + sp.c) * 2 + dir) * T;
+    const double ninf = -__builtin_huge_val();
+
+    if (lane < TP) {
+        double v0 = ninf;
+        if (lane < T) {
+            if (dir == 0) {
+                if (sp.t0 == 0) v0 = STRUCT ? (double)(a.trans[lane] + emb[lane]) : (double)Elem<TIN>::get(phib + lane);
+                else v0 = (lane == a.pin[(size_t)b * a.C + sp.c - 1]) ? 0.0 : ninf;
+            } else {
+                // a whole sequence may end in any tag; a chunk must end in its pinned tag
+                v0 = (a.chunk <= 0 || lane == a.pin[(size_t)b * a.C + sp.c]) ? 0.0 : ninf;
+            }
+        }
+        dvec[0][lane] = v0;
+    }
+    __syncthreads();
+    int buf = 0;
+    float ring[PF][RPL];
+
+    if (dir == 0) {
+        const int part = lane / TP, t = lane % TP, s0 = part * RPL;
+        const int tc = t < T ? t : T - 1;
+        float tr[STRUCT ? RPL : 1];
+        if constexpr (STRUCT) {
+#pragma unroll
+            for (int k = 0; k < RPL; ++k) tr[k] = a.trans[(size_t)(s0 + k < T ? s0 + k : T - 1) * T + tc];
+        }
+        auto load = [&](int i, int slot) {
+            if constexpr (STRUCT) {
+                ring[slot][0] = emb[(size_t)i * T + tc];
+            } else {
+                const TIN* m = phib + (size_t)i * TT + tc;
+#pragma unroll
+                for (int k = 0; k < RPL; ++k) ring[slot][k] = Elem<TIN>::get(m + (size_t)(s0 + k < T ? s0 + k : T - 1) * T);
+            }
+        };
+        walk<PF>(p0 + 1, h, +1, load, [&](int i, int slot) {
+            double val[RPL];
+            int arg[RPL];
+#pragma unroll
+            for (int k = 0; k < RPL; ++k) {
+                const int s = s0 + k;
+                const float x = STRUCT ? tr[k] + ring[slot][0] : ring[slot][k];
+                // the vector is read whatever the entry is (tags >= T hold -inf there): no branch around the LDS read
+                val[k] = dvec[buf][s] + (double)((s < T && t < T) ? x : LCCRF_NEG_INF);
+                arg[k] = s;
+            }
+            first_max_tree<RPL>(val, arg);
+            double bv = val[0];
+            int ba = bv == ninf ? kNoArg : arg[0];
+#pragma unroll
+            for (int off = TP; off < 64; off <<= 1) {
+                const double pv = __shfl_xor(bv, off, 64);
+                const int pa = __shfl_xor(ba, off, 64);
+                take_better(bv, ba, pv, pa);
+            }
+            if (part == 0) {
+                dvec[buf ^ 1][t] = bv;
+                if (t < T) bpb[(size_t)i * T + t] = (uint8_t)(ba == kNoArg ? 0 : ba);
+            }
+            __syncthreads();
+            buf ^= 1;
+        });
+    } else {
+        const int s = lane / LPC, part = lane % LPC, c0 = part * RPL;
+        const int sc = s < T ? s : T - 1;
+        float tr[STRUCT ? RPL : 1];
+        if constexpr (STRUCT) {
+#pragma unroll
+            for (int k = 0; k < RPL; ++k) tr[k] = a.trans[(size_t)sc * T + (c0 + k < T ? c0 + k : T - 1)];
+        }
+        auto load = [&](int i, int slot) {
+            const float* erow = STRUCT ? emb + (size_t)i * T : nullptr;
+            const TIN* row = STRUCT ? nullptr : phib + (size_t)i * TT + (size_t)sc * T;
+            if constexpr (ALIGNED) {
+#pragma unroll
+                for (int k = 0; k < RPL; k += 4) {
+                    float q[4];
+                    const int c = c0 + k < T ? c0 + k : T - 4;  // T % 4 == 0 here
+                    if constexpr (STRUCT) Elem<float>::get4(erow + c, q);
+                    else Elem<TIN>::get4(row + c, q);
+                    ring[slot][k] = q[0]; ring[slot][k + 1] = q[1]; ring[slot][k + 2] = q[2]; ring[slot][k + 3] = q[3];
+                }
+            } else {
+#pragma unroll
+                for (int k = 0; k < RPL; ++k) {
+                    const int c = c0 + k < T ? c0 + k : T - 1;
+                    ring[slot][k] = STRUCT ? erow[c] : Elem<TIN>::get(row + c);
+                }
+            }
+        };
+        walk<PF>(e, h + 1, -1, load, [&](int i, int slot) {
+            double val[RPL];
+            int arg[RPL];
+#pragma unroll
+            for (int k = 0; k < RPL; ++k) {
+                const int t = c0 + k;
+                const float x = STRUCT ? tr[k] + ring[slot][k] : ring[slot][k];
+                val[k] = (double)((s < T && t < T) ? x : LCCRF_NEG_INF) + dvec[buf][t];
+                arg[k] = t;
+            }
+            first_max_tree<RPL>(val, arg);
+            double bv = val[0];
+            int ba = bv == ninf ? kNoArg : arg[0];
+#pragma unroll
+            for (int off = 1; off < LPC; off <<= 1) {
+                const double pv = __shfl_xor(bv, off, 64);
+                const int pa = __shfl_xor(ba, off, 64);
+                take_better(bv, ba, pv, pa);
+            }
+            if (part == 0) {
+                dvec[buf ^ 1][s] = bv;
+                if (s < T) bpb[(size_t)i * T + s] = (uint8_t)(ba == kNoArg ? 0 : ba);
+            }
+            __syncthreads();
+            buf ^= 1;
+        });
+    }
+    if (lane < T) mid[lane] = dvec[buf][lane];
+}
+
 // Joins the two chains at the meeting point and reads off the path.
 __global__ __launch_bounds__(128) void viterbi_trace_kernel(VitArgs a) {
     __shared__ uint8_t window[2][kTraceBytes];
@@ -420,13 +577,20 @@ static hipError_t launch_geo(const VitArgs& a, hipStream_t st) {
     return hipGetLastError();
 }
 
+template <int TP, typename TIN, bool ALIGNED, bool STRUCT>
+static hipError_t launch_wave_vit(const VitArgs& a, hipStream_t st) {
+    hipLaunchKernelGGL((viterbi_wave_kernel<TP, TIN, ALIGNED, STRUCT>), dim3(2 * a.B * a.C), dim3(64), 0, st, a);
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(viterbi_trace_kernel, dim3(a.B * a.C), dim3(128), 0, st, a);
+    return hipGetLastError();
+}
+
 template <typename TIN, bool ALIGNED>
 static hipError_t launch_T(const VitArgs& a, hipStream_t st) {
     const int T = a.T;
-    if (T <= 4) return launch_geo<Geo<1, 1, 1>, TIN, ALIGNED>(a, st);
-    if (T <= 8) return launch_geo<Geo<2, 1, 1>, TIN, ALIGNED>(a, st);
-    if (T <= 16) return launch_geo<Geo<4, 1, 1>, TIN, ALIGNED>(a, st);
-    if (T <= 32) return launch_geo<Geo<8, 4, 1>, TIN, ALIGNED>(a, st);
+    if (T <= 16) return launch_wave_vit<16, TIN, ALIGNED, false>(a, st);
+    if (T <= 32) return launch_wave_vit<32, TIN, ALIGNED, false>(a, st);
     if (T <= 64) return launch_geo<Geo<16, 4, 4>, TIN, ALIGNED>(a, st);
     if (T <= 128) return launch_geo<Geo<32, 16, 4>, TIN, ALIGNED>(a, st);
     return launch_geo<Geo<64, 16, 16>, TIN, ALIGNED>(a, st);
@@ -455,10 +619,8 @@ static hipError_t launch_structured_geo(const VitArgs& a, hipStream_t st) {
 }
 template <bool ALIGNED>
 static hipError_t launch_structured_T(const VitArgs& a, hipStream_t st) {
-    if (a.T <= 4) return launch_structured_geo<Geo<1, 1, 1>, ALIGNED>(a, st);
-    if (a.T <= 8) return launch_structured_geo<Geo<2, 1, 1>, ALIGNED>(a, st);
-    if (a.T <= 16) return launch_structured_geo<Geo<4, 1, 1>, ALIGNED>(a, st);
-    if (a.T <= 32) return launch_structured_geo<Geo<8, 4, 1>, ALIGNED>(a, st);
+    if (a.T <= 16) return launch_wave_vit<16, float, ALIGNED, true>(a, st);
+    if (a.T <= 32) return launch_wave_vit<32, float, ALIGNED, true>(a, st);
     return launch_structured_geo<Geo<16, 4, 4>, ALIGNED>(a, st);
 }
 
