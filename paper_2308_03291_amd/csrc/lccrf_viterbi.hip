@@ -150,7 +150,7 @@ __global__ __launch_bounds__(G::W) void viterbi_half_kernel(VitArgs a) {
 #pragma unroll
         for (int k = 0; k < ITEMS; ++k) {
             const int s = r0 + k * G::RPP;
-            const double dk = (s < T) ? sm.dvec[buf][s] : ninf;
+            const double dk = sm.dvec[buf][s];  // s < TCAP; tags >= T hold -inf: no branch around the read
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
                 const double val = dk + (double)v[k][j];
@@ -158,13 +158,12 @@ __global__ __launch_bounds__(G::W) void viterbi_half_kernel(VitArgs a) {
             }
         }
 #pragma unroll
-        for (int off = G::LPR; off < 64; off <<= 1) {
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const double pv = __shfl_xor(best[j], off, 64);
-                const int pa = __shfl_xor(arg[j], off, 64);
-                take_better(best[j], arg[j], pv, pa);
-            }
+        for (int j = 0; j < 4; ++j) {  // over the row groups of the wave: lanes LPR, 2 LPR, ... apart
+            Best x{best[j], arg[j]};
+            if (G::LPR <= 16) x = swap_best<16>(x);
+            if (G::LPR <= 32) x = swap_best<32>(x);
+            best[j] = x.v;
+            arg[j] = x.a;
         }
         if (lane < G::LPR) {
 #pragma unroll
@@ -192,7 +191,7 @@ __global__ __launch_bounds__(G::W) void viterbi_half_kernel(VitArgs a) {
         mask_tile<G>(v, T, c4, r0);
         double ek[4];
 #pragma unroll
-        for (int j = 0; j < 4; ++j) ek[j] = (c4 + j < T) ? sm.dvec[buf][c4 + j] : ninf;
+        for (int j = 0; j < 4; ++j) ek[j] = sm.dvec[buf][c4 + j];  // -inf for tags >= T
         if constexpr (ITEMS % 4 == 0 && G::LPR >= 16) {
             // four rows at a time: each lane ends up with the winner of one of them
             const int kk = 2 * (lane & 1) + ((lane >> 1) & 1);
