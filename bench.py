@@ -74,13 +74,18 @@ def cpu_baseline(w, budget_s: float = 20.0):
     import torch
     phi = torch.stack([workloads.phi_sequence(w, b, trans) for b in range(nseq)]).contiguous()
     sample_lens = lens[:nseq].numpy()
-    t0 = time.perf_counter()
-    oracle.marginals(phi, sample_lens)
-    dt = time.perf_counter() - t0
+    cores = int(min(threads, nseq))
+    # the same pass again until about 10 s of CPU work have been timed (a workload smaller than that is repeated)
+    dt, reps = 0.0, 0
+    while reps == 0 or (dt * cores < 10.0 and reps < 64):
+        t0 = time.perf_counter()
+        oracle.marginals(phi, sample_lens)
+        dt += time.perf_counter() - t0
+        reps += 1
     pots = nseq * w.N * w.T * w.T
-    return {"value": pots / dt, "unit": "potentials/s", "cores": int(min(threads, nseq)), "kind": "oracle",
+    return {"value": reps * pots / dt, "unit": "potentials/s", "cores": cores, "kind": "oracle",
             "sample": f"fp64 oracle marginals on the first {nseq} of {w.B} sequences of {w.key} "
-                      f"({pots} potentials, {dt:.2f} s wall, OpenMP over sequences)"}
+                      f"({pots} potentials a pass, {reps} passes, {dt:.2f} s wall, OpenMP over sequences)"}
 
 
 def main():
