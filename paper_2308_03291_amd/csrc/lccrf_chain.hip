@@ -882,7 +882,7 @@ template <typename TIN, bool ALIGNED>
 static hipError_t launch_T(int op, const ChainArgs& a, hipStream_t st, hipEvent_t between, const PairPlan& pair) {
     const int T = a.T;  // T <= 32 is served by the one-wave kernels (launch_wave)
     if (T <= 64) return launch_geo<Geo<16, 4, 4>, TIN, ALIGNED, 4, 3>(op, a, st, between, pair);
-    if (T <= 128) return launch_geo<Geo<32, 16, 4>, TIN, ALIGNED, 4, 3>(op, a, st, between, pair);
+    if (T <= 128) return launch_geo<Geo<32, 16, 4>, TIN, ALIGNED, 4, 2>(op, a, st, between, pair);
     return launch_geo<Geo<64, 16, 16>, TIN, ALIGNED, 1, 1>(op, a, st, between, pair);
 }
 
