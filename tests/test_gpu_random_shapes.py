@@ -1,0 +1,46 @@
+"""A seeded sweep over many random shapes, length mixes, scales and both input types: every query
+against the CPU oracle, with the scan's chunk size varied too.  The systematic tests cover the
+known boundaries one by one; this one looks for interactions between them."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2308_03291_amd import workloads
+from test_gpu_parity import check_case, crf  # noqa: F401  (fixture)
+
+pytestmark = pytest.mark.gpu
+
+
+def _cases(seed, count):
+    rng = np.random.default_rng(seed)
+    out = []
+    for k in range(count):
+        T = int(rng.choice([1, 2, 3, 4, 5, 7, 8, 12, 15, 16, 17, 24, 31, 32, 33, 40, 48, 63, 64, 65, 96, 127, 128, 129, 160]))
+        if T <= 32 and rng.random() < 0.4:
+            N = int(rng.integers(256, 900))          # long enough for the scan under AUTO
+            B = int(rng.integers(1, 4))
+        else:
+            N = int(rng.integers(1, max(2, min(200, 6000 // T))))
+            B = int(rng.integers(1, 7))
+        scale = float(rng.choice([0.3, 1.0, 3.0, 8.0]))
+        dtype = "bf16" if rng.random() < 0.3 else "f32"
+        ragged = rng.random() < 0.7
+        chunk = int(rng.choice([0, 0, 4, 9, 16, 64]))
+        out.append((k, B, N, T, scale, dtype, ragged, chunk))
+    return out
+
+
+@pytest.mark.parametrize("k,B,N,T,scale,dtype,ragged,chunk", _cases(20230803, 120))
+def test_random_shape(crf, oracle_mod, k, B, N, T, scale, dtype, ragged, chunk):
+    phi, lens = workloads.random_case(70000 + k, B, N, T, scale=scale, ragged=ragged, min_len=0, dtype=dtype)
+    crf.set_scan_chunk(chunk)
+    try:
+        what = f"case {k}: B={B} N={N} T={T} scale={scale} {dtype} chunk={chunk}"
+        check_case(crf, oracle_mod, phi, lens if ragged else None, poison=(dtype == "f32"), what=what)
+        lens_np = lens.numpy() if ragged else None
+        dl = lens.cuda() if ragged else None
+        H = crf.lccrf_entropy(phi.cuda(), dl).cpu().numpy().astype(np.float64)
+        want = oracle_mod.entropy(phi, lens_np)
+        assert np.all(np.abs(H - want) <= 2e-4 * np.maximum(1.0, np.abs(want))), f"{what}: entropy {H} vs {want}"
+    finally:
+        crf.set_scan_chunk(0)
