@@ -343,6 +343,10 @@ template <typename G, bool WITH_MU, bool ALIGNED>
 __device__ __forceinline__ void fwd_advance(ChainSmem<G>& sm, int& buf, int& nstep, bool exact_only, int tid, int c4,
                                             int r0, int T, float (&v)[G::ITEMS][4], const float (&ua)[G::ITEMS],
                                             float c, const float (&ubK)[4], float* __restrict__ mu_out) {
+    // 64 potentials a thread and tile (T > 128), second pass: the speculative step would have to
+    // keep the tile intact beside its own values and the marginals' factors for a possible replay,
+    // which does not fit the registers; the exact step works in place.
+    if constexpr (G::ITEMS >= 16 && WITH_MU) exact_only = true;
     bool replay = exact_only;
     if (!exact_only) {
         const int flag = nstep & 3;
@@ -359,6 +363,7 @@ template <typename G, bool WITH_MU, bool ALIGNED>
 __device__ __forceinline__ void bwd_advance(ChainSmem<G>& sm, int& buf, int& nstep, bool exact_only, int tid, int c4,
                                             int r0, int T, float (&v)[G::ITEMS][4], const float (&ub)[4], float c,
                                             const float (&uaK)[G::ITEMS], float* __restrict__ mu_out) {
+    if constexpr (G::ITEMS >= 16 && WITH_MU) exact_only = true;  // as in fwd_advance
     bool replay = exact_only;
     if (!exact_only) {
         const int flag = nstep & 3;

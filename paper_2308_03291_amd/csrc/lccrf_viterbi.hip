@@ -244,6 +244,14 @@ __global__ __launch_bounds__(G::W) void viterbi_half_kernel(VitArgs a) {
         const int n = (last - first) * step_dir + 1;
         if (n <= 0) return;
         int left = n;
+        if constexpr (ITEMS >= 16) {
+            // 64 potentials a thread and tile: a second tile in flight would not fit the registers
+            for (; left > 0; --left, i += step_dir) {
+                fetch(i, A);
+                step(i, A);
+            }
+            return;
+        }
         fetch(i, A);
         while (left > 0) {
             if (left > 1) fetch(i + step_dir, Bq);
