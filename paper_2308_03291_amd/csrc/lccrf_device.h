@@ -365,6 +365,26 @@ __device__ __forceinline__ void walk(int first, int last, int dir, Load load, St
     }
 }
 
+// The same walk for a step that may give up: it returns false to end the walk at once (loads
+// already issued for later positions land in ring slots nobody reads any more).
+template <int PF, typename Load, typename Step>
+__device__ __forceinline__ void walk_while(int first, int last, int dir, Load load, Step step) {
+    const int n = (last - first) * dir + 1;
+    if (n <= 0) return;
+#pragma unroll
+    for (int p = 0; p < PF; ++p) load(first + (p < n ? p : n - 1) * dir, p);
+    int done = 0;
+    while (true) {
+#pragma unroll
+        for (int p = 0; p < PF; ++p) {
+            if (!step(first + done * dir, p)) return;
+            const int ahead = done + PF;
+            load(first + (ahead < n ? ahead : n - 1) * dir, p);
+            if (++done >= n) return;
+        }
+    }
+}
+
 constexpr float kSumLo = 0x1p-60f, kSumHi = 0x1p60f;  // accepted range of a speculative sum
 __device__ __forceinline__ bool sum_in_range(float S) { return S >= kSumLo && S <= kSumHi; }  // false for NaN
 

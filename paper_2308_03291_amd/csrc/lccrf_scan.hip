@@ -86,23 +86,26 @@ __device__ __forceinline__ void chunk_range(int c, int chunk, int L, int& first,
 // Phase A.
 //
 // TP is the padded tag count (16 or 32); matrices are handled as NB x NB blocks of 16 x 16,
-// NB = TP / 16.  Lane (g = lane / 16, j = lane % 16) handles, of block (sb, tb), the entries
-// M[16 sb + g + 4v][16 tb + j], v = 0..3 (row: tag before, column: tag after); entry number
-// e = (sb NB + tb) 4 + v.  Sources hand out matrices in base-2 logarithms, -inf outside T x T;
-// every matrix may carry a common offset besides.
-template <int TP>
+// NB = TP / 16.  Lane (g = lane / 16, j = lane % 16) handles, of block (sb, tb), four entries of
+// column 16 tb + j (row: tag before, column: tag after), entry number e = (sb NB + tb) 4 + v: the rows
+// an accumulator register v of that lane holds after a 16x16x4 MFMA, which are 16 sb + g + 4v for the
+// f64 instruction (F64) and 16 sb + 4g + v for the f32 one.  Sources hand out matrices in base-2
+// logarithms, -inf outside T x T; every matrix may carry a common offset besides.
+template <int TP, bool F64 = true>
 struct ScanShape {
     static constexpr int NB = TP / 16, NE = 4 * NB * NB;
     static constexpr int LPRow = 64 / TP;    // lanes sharing a row in the row-wise layouts (exact product, phase B)
     static constexpr int CPL = TP / LPRow;   // columns per lane there
     static_assert(TP == 16 || TP == 32, "padded tag count");
-    static __device__ __forceinline__ int row(int lane, int e) { return 16 * (e / (4 * NB)) + (lane >> 4) + 4 * (e & 3); }
+    static __device__ __forceinline__ int row(int lane, int e) {
+        return 16 * (e / (4 * NB)) + (F64 ? (lane >> 4) + 4 * (e & 3) : 4 * (lane >> 4) + (e & 3));
+    }
     static __device__ __forceinline__ int col(int lane, int e) { return 16 * ((e / 4) % NB) + (lane & 15); }
 };
 
-template <typename TIN, int TP>
+template <typename TIN, int TP, bool F64>
 struct PotentialMatrices {  // the potentials phi_i of one sequence
-    using S = ScanShape<TP>;
+    using S = ScanShape<TP, F64>;
     static constexpr int PF = TP == 16 ? kScanPF : 3;
     struct Slot { float x[S::NE]; };
     const TIN* phib;
@@ -134,9 +137,9 @@ struct PotentialMatrices {  // the potentials phi_i of one sequence
     __device__ __forceinline__ double offset(int) const { return 0.0; }
 };
 
-template <int TP>
+template <int TP, bool F64>
 struct ChunkMatrices {  // the chunk products of one sequence, as phase A has written them
-    using S = ScanShape<TP>;
+    using S = ScanShape<TP, F64>;
     static constexpr int PF = TP == 16 ? 4 : 2;
     struct Slot { float p[S::NE], r[S::NE]; double b; };
     const float* Pl;
@@ -165,24 +168,69 @@ struct ChunkMatrices {  // the chunk products of one sequence, as phase A has wr
     __device__ __forceinline__ double offset(int c) const { return base[c]; }
 };
 
-// Product of matrices first .. last of `src` (none: the identity), by one wave, written as
+// The arithmetic of the linear-domain product in the two precisions it is tried in.
+constexpr int kNoExponent = -100000;  // exponent() of zero (and of subnormal numbers)
+template <bool F64>
+struct Linear;
+template <>
+struct Linear<true> {
+    using scalar = double;
+    using vec = f64x4;
+    static __device__ __forceinline__ double tiny() { return kTiny; }
+    // 2^d in double: the fraction through the float exponential, the integer part through the exponent field
+    static __device__ __forceinline__ double pow2(float d) {
+        const float di = floorf(d);
+        return d > -1000.f ? ldexp((double)ex2(d - di), (int)di) : 0.0;
+    }
+    static __device__ __forceinline__ vec mfma(double a, double b, vec c) { return __builtin_amdgcn_mfma_f64_16x16x4f64(a, b, c, 0, 0, 0); }
+    static __device__ __forceinline__ int exponent(double x) { const int f = (__double2hiint(x) >> 20) & 0x7ff; return f > 0 ? f - 1023 : kNoExponent; }
+    static __device__ __forceinline__ double scaled(double x, int e) { return ldexp(x, -e); }
+    static __device__ __forceinline__ float log2_of(double x) { return (float)log2(x); }
+};
+template <>
+struct Linear<false> {
+    using scalar = float;
+    using vec = f32x4;
+    static __device__ __forceinline__ float tiny() { return 0x1p-90f; }
+    static __device__ __forceinline__ float pow2(float d) { return ex2(d); }
+    static __device__ __forceinline__ vec mfma(float a, float b, vec c) { return __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, c, 0, 0, 0); }
+    static __device__ __forceinline__ int exponent(float x) { const int f = (__float_as_int(x) >> 23) & 0xff; return f > 0 ? f - 127 : kNoExponent; }
+    static __device__ __forceinline__ float scaled(float x, int e) { return ldexpf(x, -e); }
+    static __device__ __forceinline__ float log2_of(float x) { return lg2(x); }
+};
+
+// Product of matrices first .. last of `src` (none: the identity) in the linear domain on the matrix
+// cores, by one wave; written, if accepted (the return value), as
 // log2 P[r][s] = Pout[s * TP + r] + rel_out[r] + *base_out.
-template <int TP, typename Src>
-__device__ __forceinline__ void matrix_product(const Src& src, int first, int last, int T, float* __restrict__ Pout,
-                                               float* __restrict__ rel_out, double* __restrict__ base_out,
-                                               float (*Pc)[TP + 1], float (*Ph)[TP + 1]) {
-    using S = ScanShape<TP>;
+// Block (sb, rb) of D (exit tag s, entry tag r) sits in the accumulator layout of the 16x16x4
+// MFMA of its precision: lane (g, j) holds D[row(v)][16 rb + j], v = 0..3.  The same lane loads
+// phi_i[row(v)][16 tb + j]; as the A operand of an MFMA that is E^T[j][k = g] for the inner
+// indices s = row(v), and register v of D's block (sb, rb) is the matching B operand, so block
+// (tb, rb) of
+//     D_new[t][r] = sum_s E[s][t] D[s][r]
+// is the sum over sb and v of those MFMAs, and nothing moves between lanes from one position
+// to the next.  F64 = false is the product in single precision (half the matrix time and no
+// double-precision conversions); its narrower exponent range makes it give up on peaked
+// potentials, which take the double-precision product from the start.
+//
+// Which products try single precision first.  Measured on independent normal potentials: with 17 to
+// 32 tags it takes a quarter off the scan's log-partition (all kernels) up to a standard deviation
+// of 7, costs nothing at 8 to 9 and adds a tenth to a fifth from 10 on, where some wave of the
+// launch gives up late in its chunk; with up to 16 tags the matrix cores are a small part of the
+// time, the gain is half as large and the same loss would fall on long chains of peaked
+// potentials, so those stay in double precision.
+template <int TP>
+constexpr bool kSingleFirst = TP == 32;
+
+template <int TP, bool F64, typename Src>
+__device__ __forceinline__ bool linear_product(const Src& src, int first, int last, int T, float* __restrict__ Pout,
+                                               float* __restrict__ rel_out, double* __restrict__ base_out) {
+    using S = ScanShape<TP, F64>;
+    using L = Linear<F64>;
+    using scalar = typename L::scalar;
+    using vec = typename L::vec;
     constexpr int NB = S::NB, NE = S::NE;
     const int lane = threadIdx.x;
-    // ---- linear-domain product on the matrix cores, in double precision for its exponent range.
-    // Block (sb, rb) of D (exit tag s, entry tag r) sits in the accumulator layout of the 16x16x4
-    // f64 MFMA: lane (g, j) holds D[16 sb + g + 4v][16 rb + j], v = 0..3.  The same lane loads
-    // phi_i[16 sb + g + 4v][16 tb + j]; as the A operand of an MFMA that is E^T[j][k = g] for the
-    // inner indices s = 16 sb + g + 4v, and register v of D's block (sb, rb) is the matching B
-    // operand, so block (tb, rb) of
-    //     D_new[t][r] = sum_s E[s][t] D[s][r]
-    // is the sum over sb and v of those MFMAs, and nothing moves between lanes from one position
-    // to the next.
     {
         const int g = lane >> 4, j = lane & 15;
         unsigned in = 0;
@@ -190,29 +238,32 @@ __device__ __forceinline__ void matrix_product(const Src& src, int first, int la
         for (int e = 0; e < NE; ++e) in |= (S::row(lane, e) < T && S::col(lane, e) < T) ? (1u << e) : 0u;
         // The zero pattern of D (1 where some path exists) is carried along by a product of 0/1
         // matrices on the f32 MFMA, from the first matrix with a -inf entry on (until then D is
-        // the identity or has no zero).  That instruction numbers its output rows 4g + v, so it
-        // runs on rows renamed by pi(4g + v) = g + 4v: its A operand is the flag of column pi(j).
-        const int pj = (lane & 48) | (4 * (j & 3) + (j >> 2));
-        double D[NB][NB][4];
+        // the identity or has no zero).  That instruction numbers its output rows 4g + v; beside the
+        // f64 product it therefore runs on rows renamed by pi(4g + v) = g + 4v: its A operand is the
+        // flag of column pi(j).
+        const int pj = F64 ? ((lane & 48) | (4 * (j & 3) + (j >> 2))) : lane;
+        scalar D[NB][NB][4];
         float Z[NB][NB][4];
+        double Msum = 0.0;
+        int esum[NB];
+        bool bad = false, tracking = false, started = false, rejected = false;
 #pragma unroll
         for (int sb = 0; sb < NB; ++sb)
 #pragma unroll
             for (int rb = 0; rb < NB; ++rb)
 #pragma unroll
                 for (int v = 0; v < 4; ++v) {
-                    const bool diag = sb == rb && g + 4 * v == j;
-                    D[sb][rb][v] = diag ? 1.0 : 0.0;
+                    const bool diag = sb == rb && (F64 ? g + 4 * v : 4 * g + v) == j;
+                    D[sb][rb][v] = diag ? (scalar)1 : (scalar)0;
                     Z[sb][rb][v] = diag ? 1.f : 0.f;
                 }
-        typename Src::Slot ring[Src::PF];
-        auto load = [&](int i, int slot) { src.load(i, ring[slot]); };
-        double Msum = 0.0;
-        int esum[NB];
 #pragma unroll
         for (int rb = 0; rb < NB; ++rb) esum[rb] = 0;
-        bool bad = false, tracking = false, started = false;
-        walk<Src::PF>(first, last, +1, load, [&](int, int slot) {
+        typename Src::Slot ring[Src::PF];
+        auto load = [&](int i, int slot) { src.load(i, ring[slot]); };
+        // The single-precision product looks at every position whether it still holds, and ends at
+        // once if not; the double-precision one hardly ever fails and is judged at the end.
+        const auto step = [&](int, int slot) -> bool {
             float x[NE];
             const double common = src.entries(ring[slot], x);
             float mloc = x[0];
@@ -221,11 +272,11 @@ __device__ __forceinline__ void matrix_product(const Src& src, int first, int la
             const float m = finite_or_zero(xor_max<1, 64>(mloc));
             Msum += (double)m + common;
             unsigned nz = 0;
-            f64x4 acc[NB][NB];
+            vec acc[NB][NB];
 #pragma unroll
             for (int tb = 0; tb < NB; ++tb)
 #pragma unroll
-                for (int rb = 0; rb < NB; ++rb) acc[tb][rb] = f64x4{0.0, 0.0, 0.0, 0.0};
+                for (int rb = 0; rb < NB; ++rb) acc[tb][rb] = vec{0, 0, 0, 0};
 #pragma unroll
             for (int sb = 0; sb < NB; ++sb)
 #pragma unroll
@@ -233,14 +284,10 @@ __device__ __forceinline__ void matrix_product(const Src& src, int first, int la
 #pragma unroll
                     for (int v = 0; v < 4; ++v) {
                         const int e = (sb * NB + tb) * 4 + v;
-                        // E = 2^(x - m) in double: the fraction through the float exponential, the
-                        // integer part through the exponent field
-                        const float d = x[e] - m, di = floorf(d);
-                        const double E = d > -1000.f ? ldexp((double)ex2(d - di), (int)di) : 0.0;
+                        const scalar E = L::pow2(x[e] - m);
                         nz |= (x[e] > LCCRF_NEG_INF) ? (1u << e) : 0u;
 #pragma unroll
-                        for (int rb = 0; rb < NB; ++rb)
-                            acc[tb][rb] = __builtin_amdgcn_mfma_f64_16x16x4f64(E, D[sb][rb][v], acc[tb][rb], 0, 0, 0);
+                        for (int rb = 0; rb < NB; ++rb) acc[tb][rb] = L::mfma(E, D[sb][rb][v], acc[tb][rb]);
                     }
             const bool hole = (in & ~nz) != 0;
             if (!tracking && __builtin_amdgcn_ballot_w64(hole) != 0) {
@@ -280,7 +327,7 @@ __device__ __forceinline__ void matrix_product(const Src& src, int first, int la
 #pragma unroll
                         for (int v = 0; v < 4; ++v) {
                             Z[tb][rb][v] = pat[tb][rb][v] > 0.f ? 1.f : 0.f;
-                            bad |= (pat[tb][rb][v] > 0.f) & !(acc[tb][rb][v] >= kTiny);
+                            bad |= (pat[tb][rb][v] > 0.f) & !(acc[tb][rb][v] >= L::tiny());
                         }
             } else {
 #pragma unroll
@@ -289,34 +336,42 @@ __device__ __forceinline__ void matrix_product(const Src& src, int first, int la
                     for (int rb = 0; rb < NB; ++rb)
 #pragma unroll
                         for (int v = 0; v < 4; ++v)
-                            bad |= ((in >> ((tb * NB + rb) * 4 + v)) & 1) & !(acc[tb][rb][v] >= kTiny);
+                            bad |= ((in >> ((tb * NB + rb) * 4 + v)) & 1) & !(acc[tb][rb][v] >= L::tiny());
+            }
+            if (!F64 && __builtin_amdgcn_ballot_w64(bad) != 0) {
+                rejected = true;
+                return false;
             }
             // With the column maxima of D in [1, 2) and E at most 1, a term lost to underflow is
-            // below 2^-1022: it cannot matter to a sum that is at least kTiny.
-            // Power-of-two rescale of each entry tag's column (exact): the largest exponent field.
+            // below the smallest normal number: it cannot matter to a sum that is at least tiny().
+            // Power-of-two rescale of each entry tag's column (exact): the largest exponent.
 #pragma unroll
             for (int rb = 0; rb < NB; ++rb) {
-                int ef = 0;
+                int ef = kNoExponent;
 #pragma unroll
                 for (int tb = 0; tb < NB; ++tb)
 #pragma unroll
                     for (int v = 0; v < 4; ++v) {
-                        const int f = (__double2hiint(acc[tb][rb][v]) >> 20) & 0x7ff;
+                        const int f = L::exponent(acc[tb][rb][v]);
                         ef = f > ef ? f : ef;
                     }
                 const auto r16 = __builtin_amdgcn_permlane16_swap(ef, ef, false, false);
                 ef = (int)r16[0] > (int)r16[1] ? (int)r16[0] : (int)r16[1];
                 const auto r32 = __builtin_amdgcn_permlane32_swap(ef, ef, false, false);
                 ef = (int)r32[0] > (int)r32[1] ? (int)r32[0] : (int)r32[1];
-                const int ex = ef > 0 ? ef - 1023 : 0;
+                const int ex = ef > kNoExponent ? ef : 0;  // a column without any path keeps its zeros
                 esum[rb] += ex;
 #pragma unroll
                 for (int tb = 0; tb < NB; ++tb)
 #pragma unroll
-                    for (int v = 0; v < 4; ++v) D[tb][rb][v] = ldexp(acc[tb][rb][v], -ex);
+                    for (int v = 0; v < 4; ++v) D[tb][rb][v] = L::scaled(acc[tb][rb][v], ex);
             }
-        });
-        if (__builtin_amdgcn_ballot_w64(bad) == 0) {
+            return true;
+        };
+        if constexpr (F64) walk<Src::PF>(first, last, +1, load, step);
+        else walk_while<Src::PF>(first, last, +1, load, step);
+        rejected |= __builtin_amdgcn_ballot_w64(bad) != 0;
+        if (!rejected) {
             float ef[NB], emax = LCCRF_NEG_INF;
 #pragma unroll
             for (int rb = 0; rb < NB; ++rb) {
@@ -331,20 +386,29 @@ __device__ __forceinline__ void matrix_product(const Src& src, int first, int la
 #pragma unroll
                     for (int v = 0; v < 4; ++v) {
                         const bool inside = (in >> ((tb * NB + rb) * 4 + v)) & 1;
-                        Pout[(16 * tb + g + 4 * v) * TP + 16 * rb + j] =
-                            (inside && D[tb][rb][v] > 0.0) ? (float)log2(D[tb][rb][v]) : LCCRF_NEG_INF;
+                        Pout[S::row(lane, (tb * NB + rb) * 4 + v) * TP + 16 * rb + j] =
+                            (inside && D[tb][rb][v] > 0) ? L::log2_of(D[tb][rb][v]) : LCCRF_NEG_INF;
                     }
             if (g == 0) {
 #pragma unroll
                 for (int rb = 0; rb < NB; ++rb) rel_out[16 * rb + j] = ef[rb] - emax;
             }
             if (lane == 0) *base_out = Msum + (double)emax;
-            return;
+            return true;
         }
     }
+    return false;
+}
 
-    // ---- exact log-domain product (rare).  Lane (r = lane / LPRow, q = lane % LPRow) owns
-    // P[r][CPL q .. CPL q + CPL - 1]; P and the current matrix are exchanged through LDS.
+// The same product in the log domain, every log-sum-exp shifted by its own maximum (rare: taken when
+// both linear products gave up).  Lane (r = lane / LPRow, q = lane % LPRow) owns
+// P[r][CPL q .. CPL q + CPL - 1]; P and the current matrix are exchanged through LDS.
+template <int TP, typename Src>
+__device__ __forceinline__ void exact_product(const Src& src, int first, int last, int T, float* __restrict__ Pout,
+                                              float* __restrict__ rel_out, double* __restrict__ base_out,
+                                              float (*Pc)[TP + 1], float (*Ph)[TP + 1]) {
+    using S = ScanShape<TP, true>;
+    const int lane = threadIdx.x;
     {
         constexpr int LPRow = S::LPRow, CPL = S::CPL;
         const int r = lane / LPRow, q = lane % LPRow;
@@ -415,9 +479,17 @@ __global__ __launch_bounds__(64) void chunk_product_kernel(ScanArgs a) {
     if (c * a.chunk >= L) return;
     int first, last;
     chunk_range(c, a.chunk, L, first, last);
-    const PotentialMatrices<TIN, TP> src(static_cast<const TIN*>(a.phi) + (size_t)b * N * T * T, T, threadIdx.x);
+    const TIN* phib = static_cast<const TIN*>(a.phi) + (size_t)b * N * T * T;
     const size_t bc = (size_t)b * a.C + c;
-    matrix_product<TP>(src, first, last, T, a.Pl + bc * TP * TP, a.rel + bc * TP, a.base + bc, Pc, Ph);
+    float* Pout = a.Pl + bc * TP * TP;
+    float* rel_out = a.rel + bc * TP;
+    if constexpr (kSingleFirst<TP>) {
+        const PotentialMatrices<TIN, TP, false> src(phib, T, threadIdx.x);
+        if (linear_product<TP, false>(src, first, last, T, Pout, rel_out, a.base + bc)) return;
+    }
+    const PotentialMatrices<TIN, TP, true> src(phib, T, threadIdx.x);
+    if (linear_product<TP, true>(src, first, last, T, Pout, rel_out, a.base + bc)) return;
+    exact_product<TP>(src, first, last, T, Pout, rel_out, a.base + bc, Pc, Ph);
 }
 
 // One wave per group of GS chunks: the product of the group's chunk products.
@@ -432,8 +504,15 @@ __global__ __launch_bounds__(64) void group_product_kernel(ScanArgs a) {
     if (c0 >= Cb) return;
     const int c1 = (c0 + a.GS < Cb ? c0 + a.GS : Cb) - 1;
     const size_t cb = (size_t)b * a.C, bg = (size_t)b * a.G + g;
-    const ChunkMatrices<TP> src(a.Pl + cb * TP * TP, a.rel + cb * TP, a.base + cb, a.T, threadIdx.x);
-    matrix_product<TP>(src, c0, c1, a.T, a.Pl2 + bg * TP * TP, a.rel2 + bg * TP, a.base2 + bg, Pc, Ph);
+    float* Pout = a.Pl2 + bg * TP * TP;
+    float* rel_out = a.rel2 + bg * TP;
+    if constexpr (kSingleFirst<TP>) {
+        const ChunkMatrices<TP, false> src(a.Pl + cb * TP * TP, a.rel + cb * TP, a.base + cb, a.T, threadIdx.x);
+        if (linear_product<TP, false>(src, c0, c1, a.T, Pout, rel_out, a.base2 + bg)) return;
+    }
+    const ChunkMatrices<TP, true> src(a.Pl + cb * TP * TP, a.rel + cb * TP, a.base + cb, a.T, threadIdx.x);
+    if (linear_product<TP, true>(src, c0, c1, a.T, Pout, rel_out, a.base2 + bg)) return;
+    exact_product<TP>(src, c0, c1, a.T, Pout, rel_out, a.base2 + bg, Pc, Ph);
 }
 
 // ---------------------------------------------------------------------------------------
@@ -448,7 +527,7 @@ __global__ __launch_bounds__(64) void group_product_kernel(ScanArgs a) {
 // instructions.
 template <typename TIN, int TP>
 __global__ __launch_bounds__(64) void chunk_boundary_kernel(ScanArgs a) {
-    using S = ScanShape<TP>;
+    using S = ScanShape<TP, true>;
     constexpr int LPRow = S::LPRow, CPL = S::CPL, PF = TP == 16 ? kScanPF : 4;
     const int lane = threadIdx.x, o = lane / LPRow, q = lane % LPRow;
     const int dir = blockIdx.x & 1;

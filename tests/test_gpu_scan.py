@@ -170,6 +170,17 @@ def test_scan_32_tags_bf16_forbidden_edges_jumps_and_offsets(crf, oracle_mod, ch
     check_case(crf, oracle_mod, (phi + 40.0).contiguous(), lens, algo=crf.ALGO_SCAN, what="scan T=24 offsets", queries=SUMS)
 
 
+@pytest.mark.parametrize("scale", [5.0, 8.0, 10.0, 12.0])
+@pytest.mark.parametrize("T", [19, 32])
+def test_scan_32_tags_precision_ladder(crf, oracle_mod, chunk, T, scale):
+    """Chunk products of 17 .. 32 tags start in single precision and pass to double precision where
+    their exponent range runs out: scales on both sides of that boundary (it lies near 8), long
+    chunks, so that some chunks give up late and others never, and group products above them."""
+    chunk(32)
+    phi, lens = workloads.random_case(5950 + T, 3, 2100, T, scale=scale, ragged=True, min_len=1500)
+    check_case(crf, oracle_mod, phi, lens, algo=crf.ALGO_SCAN, what=f"scan T={T} scale {scale}", queries=SUMS)
+
+
 def test_scan_32_tags_agrees_with_sequential_on_the_paper_shape(crf):
     w = workloads.WORKLOADS["paper_lccrf"]
     dphi = workloads.phi_batch(w).cuda()
