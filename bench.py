@@ -96,6 +96,10 @@ def main():
     ap.add_argument("--workload", default="cfg4")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-other-queries", action="store_true")
+    ap.add_argument("--cold", action="store_true",
+                    help="write a 512 MB scratch buffer before every timed call, so that nothing of the "
+                         "workload is left in L2 or the 256 MB memory-side cache (matters for workloads "
+                         "smaller than that; times then come from the per-call events, not the wall clock)")
     ap.add_argument("--pmc-calibration", action="store_true",
                     help="also run one plain elementwise kernel of known size (reads and writes exactly "
                          "4 bytes per potential) so that rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE "
@@ -140,7 +144,14 @@ def main():
         torch.cuda.synchronize()
         return evs
 
+    scratch = torch.empty(512 << 20, dtype=torch.uint8, device=dev) if args.cold else None
+
+    def evict():
+        if scratch is not None:
+            scratch.add_(1)
+
     def run_step(evs=None):
+        evict()
         if evs is None:
             crf.lccrf_marginals(phi, lens, out=mu, logZ=lz, workspace=ws)
         else:
@@ -158,10 +169,11 @@ def main():
         run_step(evs)
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
-    ms_per_step = wall * 1e3 / args.steps
     pass1 = [e[0].elapsed_time(e[1]) for e in per_step_events]
     pass2 = [e[1].elapsed_time(e[2]) for e in per_step_events]
     whole = [e[0].elapsed_time(e[2]) for e in per_step_events]
+    # cold runs: the wall clock also holds the scratch writes, the events only the calls
+    ms_per_step = sum(whole) / len(whole) if args.cold else wall * 1e3 / args.steps
     pass2_avg = sum(pass2) / len(pass2)
     log(f"[bench] {args.steps} steps: wall {ms_per_step:.4f} ms/step; events: call avg {sum(whole) / len(whole):.4f} ms "
         f"(pass 1 {sum(pass1) / len(pass1):.4f}, pass 2 {pass2_avg:.4f}), median call {median(whole):.4f} ms")
@@ -219,6 +231,7 @@ def main():
                 fn()
             evs = new_events(2 * max(5, args.steps // 2))
             for k in range(0, len(evs), 2):
+                evict()
                 evs[k].record()
                 fn()
                 evs[k + 1].record()
@@ -243,7 +256,8 @@ def main():
         "data": "synthetic",
         "config": {"workload": f"{w.key}: B={w.B} N={w.N} T={w.T} {w.dtype} phi, lengths U[{w.len_lo},{w.len_hi}], "
                                f"seeded {w.kind} potentials (scale {w.scale})",
-                   "query": "lccrf_marginals (logZ + all edge marginals)", "potentials": pots,
+                   "query": "lccrf_marginals (logZ + all edge marginals)", "caches": "cold" if args.cold else "warm",
+                   "potentials": pots,
                    "effective_potentials": eff_pots},
         "roofline": roofline, "cpu_baseline": base,
     }
