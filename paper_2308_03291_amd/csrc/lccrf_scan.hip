@@ -35,7 +35,6 @@ namespace lccrf {
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef double f64x4 __attribute__((ext_vector_type(4)));
 
-constexpr double kTiny = 0x1p-900;  // smallest accepted entry of a linear-domain product
 constexpr int kScanPF = 8;
 
 // Value of lane `src_lane` (any lane, computed per lane).
@@ -108,6 +107,8 @@ struct PotentialMatrices {  // the potentials phi_i of one sequence
     using S = ScanShape<TP, F64>;
     static constexpr int PF = TP == 16 ? kScanPF : 3;
     struct Slot { float x[S::NE]; };
+    // entries outside T x T are loaded from the nearest entry inside: whatever a slot holds is a potential
+    static constexpr bool kPaddingIsFinite = true;
     const TIN* phib;
     int T;
     size_t TT;
@@ -131,6 +132,12 @@ struct PotentialMatrices {  // the potentials phi_i of one sequence
         for (int e = 0; e < S::NE; ++e) x[e] = (in >> e) & 1 ? sl.x[e] * kLog2e : LCCRF_NEG_INF;
         return 0.0;
     }
+    __device__ __forceinline__ float smallest_loaded(const Slot& sl) const {
+        float lo = sl.x[0];
+#pragma unroll
+        for (int e = 1; e < S::NE; ++e) lo = fminf(lo, sl.x[e]);
+        return lo;
+    }
     __device__ __forceinline__ float entry(int i, int r, int t) const {  // one entry, straight from memory
         return (r < T && t < T) ? Elem<TIN>::get(phib + (size_t)i * TT + r * T + t) * kLog2e : LCCRF_NEG_INF;
     }
@@ -142,6 +149,7 @@ struct ChunkMatrices {  // the chunk products of one sequence, as phase A has wr
     using S = ScanShape<TP, F64>;
     static constexpr int PF = TP == 16 ? 4 : 2;
     struct Slot { float p[S::NE], r[S::NE]; double b; };
+    static constexpr bool kPaddingIsFinite = false;  // stored products are -inf outside T x T
     const float* Pl;
     const float* rel;
     const double* base;
@@ -169,21 +177,21 @@ struct ChunkMatrices {  // the chunk products of one sequence, as phase A has wr
 };
 
 // The arithmetic of the linear-domain product in the two precisions it is tried in.
-constexpr int kNoExponent = -100000;  // exponent() of zero (and of subnormal numbers)
 template <bool F64>
 struct Linear;
 template <>
 struct Linear<true> {
     using scalar = double;
     using vec = f64x4;
-    static __device__ __forceinline__ double tiny() { return kTiny; }
     // 2^d in double: the fraction through the float exponential, the integer part through the exponent field
     static __device__ __forceinline__ double pow2(float d) {
         const float di = floorf(d);
         return d > -1000.f ? ldexp((double)ex2(d - di), (int)di) : 0.0;
     }
     static __device__ __forceinline__ vec mfma(double a, double b, vec c) { return __builtin_amdgcn_mfma_f64_16x16x4f64(a, b, c, 0, 0, 0); }
-    static __device__ __forceinline__ int exponent(double x) { const int f = (__double2hiint(x) >> 20) & 0x7ff; return f > 0 ? f - 1023 : kNoExponent; }
+    // exponent field of a non-negative number; entries below 2^-900 are not accepted
+    static constexpr unsigned kBias = 1023, kMinField = 1023 - 900, kNoField = 0x7ff;
+    static __device__ __forceinline__ unsigned field(double x) { return __builtin_amdgcn_ubfe((unsigned)__double2hiint(x), 20, 11); }
     static __device__ __forceinline__ double scaled(double x, int e) { return ldexp(x, -e); }
     static __device__ __forceinline__ float log2_of(double x) { return (float)log2(x); }
 };
@@ -191,10 +199,11 @@ template <>
 struct Linear<false> {
     using scalar = float;
     using vec = f32x4;
-    static __device__ __forceinline__ float tiny() { return 0x1p-90f; }
     static __device__ __forceinline__ float pow2(float d) { return ex2(d); }
     static __device__ __forceinline__ vec mfma(float a, float b, vec c) { return __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, c, 0, 0, 0); }
-    static __device__ __forceinline__ int exponent(float x) { const int f = (__float_as_int(x) >> 23) & 0xff; return f > 0 ? f - 127 : kNoExponent; }
+    // entries below 2^-90 are not accepted: with them a term that underflowed could matter
+    static constexpr unsigned kBias = 127, kMinField = 127 - 90, kNoField = 0xff;
+    static __device__ __forceinline__ unsigned field(float x) { return __builtin_amdgcn_ubfe((unsigned)__float_as_int(x), 23, 8); }
     static __device__ __forceinline__ float scaled(float x, int e) { return ldexpf(x, -e); }
     static __device__ __forceinline__ float log2_of(float x) { return lg2(x); }
 };
@@ -271,7 +280,6 @@ __device__ __forceinline__ bool linear_product(const Src& src, int first, int la
             for (int e = 1; e < NE; ++e) mloc = fmaxf(mloc, x[e]);
             const float m = finite_or_zero(xor_max<1, 64>(mloc));
             Msum += (double)m + common;
-            unsigned nz = 0;
             vec acc[NB][NB];
 #pragma unroll
             for (int tb = 0; tb < NB; ++tb)
@@ -283,13 +291,25 @@ __device__ __forceinline__ bool linear_product(const Src& src, int first, int la
                 for (int tb = 0; tb < NB; ++tb)
 #pragma unroll
                     for (int v = 0; v < 4; ++v) {
-                        const int e = (sb * NB + tb) * 4 + v;
-                        const scalar E = L::pow2(x[e] - m);
-                        nz |= (x[e] > LCCRF_NEG_INF) ? (1u << e) : 0u;
+                        const scalar E = L::pow2(x[(sb * NB + tb) * 4 + v] - m);
 #pragma unroll
                         for (int rb = 0; rb < NB; ++rb) acc[tb][rb] = L::mfma(E, D[sb][rb][v], acc[tb][rb]);
                     }
-            const bool hole = (in & ~nz) != 0;
+            // bit e of nz: entry e of this matrix is not a structural zero
+            const auto nonzero_mask = [&]() {
+                unsigned nz = 0;
+#pragma unroll
+                for (int e = 0; e < NE; ++e) nz |= (x[e] > LCCRF_NEG_INF) ? (1u << e) : 0u;
+                return nz;
+            };
+            unsigned nz = 0;
+            bool hole;
+            if constexpr (Src::kPaddingIsFinite) {
+                hole = src.smallest_loaded(ring[slot]) == LCCRF_NEG_INF;
+            } else {
+                nz = nonzero_mask();
+                hole = (in & ~nz) != 0;
+            }
             if (!tracking && __builtin_amdgcn_ballot_w64(hole) != 0) {
                 tracking = true;
                 if (started) {
@@ -302,7 +322,17 @@ __device__ __forceinline__ bool linear_product(const Src& src, int first, int la
                 }
             }
             started = true;
+            // Exponent fields of the new entries: their largest gives each column's rescale, the
+            // smallest among the entries that some path reaches says whether the product still holds.
+            unsigned fld[NB][NB][4], fmin = L::kNoField;
+#pragma unroll
+            for (int tb = 0; tb < NB; ++tb)
+#pragma unroll
+                for (int rb = 0; rb < NB; ++rb)
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) fld[tb][rb][v] = L::field(acc[tb][rb][v]);
             if (tracking) {
+                if constexpr (Src::kPaddingIsFinite) nz = nonzero_mask();
                 const unsigned nzp = (unsigned)__shfl((int)nz, pj, 64);
                 f32x4 pat[NB][NB];
 #pragma unroll
@@ -326,8 +356,9 @@ __device__ __forceinline__ bool linear_product(const Src& src, int first, int la
                     for (int rb = 0; rb < NB; ++rb)
 #pragma unroll
                         for (int v = 0; v < 4; ++v) {
-                            Z[tb][rb][v] = pat[tb][rb][v] > 0.f ? 1.f : 0.f;
-                            bad |= (pat[tb][rb][v] > 0.f) & !(acc[tb][rb][v] >= L::tiny());
+                            const bool reached = pat[tb][rb][v] > 0.f;
+                            Z[tb][rb][v] = reached ? 1.f : 0.f;
+                            fmin = min(fmin, reached ? fld[tb][rb][v] : L::kNoField);
                         }
             } else {
 #pragma unroll
@@ -336,30 +367,28 @@ __device__ __forceinline__ bool linear_product(const Src& src, int first, int la
                     for (int rb = 0; rb < NB; ++rb)
 #pragma unroll
                         for (int v = 0; v < 4; ++v)
-                            bad |= ((in >> ((tb * NB + rb) * 4 + v)) & 1) & !(acc[tb][rb][v] >= L::tiny());
+                            fmin = min(fmin, (in >> ((tb * NB + rb) * 4 + v)) & 1 ? fld[tb][rb][v] : L::kNoField);
             }
+            bad |= fmin < L::kMinField;  // also zero and subnormal entries (field 0)
             if (!F64 && __builtin_amdgcn_ballot_w64(bad) != 0) {
                 rejected = true;
                 return false;
             }
             // With the column maxima of D in [1, 2) and E at most 1, a term lost to underflow is
-            // below the smallest normal number: it cannot matter to a sum that is at least tiny().
+            // below the smallest normal number: it cannot matter to a sum of the accepted size.
             // Power-of-two rescale of each entry tag's column (exact): the largest exponent.
 #pragma unroll
             for (int rb = 0; rb < NB; ++rb) {
-                int ef = kNoExponent;
+                unsigned ef = 0;
 #pragma unroll
                 for (int tb = 0; tb < NB; ++tb)
 #pragma unroll
-                    for (int v = 0; v < 4; ++v) {
-                        const int f = L::exponent(acc[tb][rb][v]);
-                        ef = f > ef ? f : ef;
-                    }
+                    for (int v = 0; v < 4; ++v) ef = max(ef, fld[tb][rb][v]);
                 const auto r16 = __builtin_amdgcn_permlane16_swap(ef, ef, false, false);
-                ef = (int)r16[0] > (int)r16[1] ? (int)r16[0] : (int)r16[1];
+                ef = max(r16[0], r16[1]);
                 const auto r32 = __builtin_amdgcn_permlane32_swap(ef, ef, false, false);
-                ef = (int)r32[0] > (int)r32[1] ? (int)r32[0] : (int)r32[1];
-                const int ex = ef > kNoExponent ? ef : 0;  // a column without any path keeps its zeros
+                ef = max(r32[0], r32[1]);
+                const int ex = ef > 0 ? (int)ef - (int)L::kBias : 0;  // a column without any path keeps its zeros
                 esum[rb] += ex;
 #pragma unroll
                 for (int tb = 0; tb < NB; ++tb)
