@@ -698,12 +698,25 @@ struct MaxScanArgs {
     const int32_t* pin_in;
 };
 
+// A double of lane `K` of every aligned group of four lanes.
+template <int K>
+__device__ __forceinline__ double quad_read(double x) {
+    const long long bits = __double_as_longlong(x);
+    const int lo = dpp_i<K * 0x55>((int)(bits & 0xffffffffll)), hi = dpp_i<K * 0x55>((int)(bits >> 32));
+    return __longlong_as_double(((long long)hi << 32) | (unsigned int)lo);
+}
+
 // Max-plus product of matrices first .. last (none: the identity) by one wave.  Lane
-// (r = lane / 4, q = lane % 4) owns M[r][4q .. 4q+3] and stages X_i[r][4q .. 4q+3] of every
-// matrix through LDS.  get(i, jj) returns this lane's four entries of matrix i.
-template <int PF, typename Slot, typename Load, typename Get>
+// (r = lane / 4, q = lane % 4) owns M[r][4q .. 4q+3]; row r of M is spread over the four lanes of a
+// quad and is read from their registers, the entries X_i[s][4q .. 4q+3] of every matrix, which the
+// sixteen lanes of column group q all need, go through LDS in the type XT they are stored in
+// (potentials as floats: the conversion to double is repeated by every reader, half the LDS bytes
+// are what eight such waves on a compute unit wait for).  get(slot, jj) returns this lane's four
+// entries of a matrix.  One wave per workgroup: the barrier is only the wait for the LDS writes, and
+// the two tile buffers keep the next matrix's writes off the tile that is being read.
+template <int PF, typename Slot, typename XT, typename Load, typename Get>
 __device__ __forceinline__ void maxplus_product(int first, int last, int T, double* __restrict__ out, Load load_slot,
-                                                Get get, double (*Mc)[18], double (*Xs)[16]) {
+                                                Get get, XT (*Xs)[16][16]) {
     const int lane = threadIdx.x, r = lane >> 2, q = lane & 3;
     const double ninf = -__builtin_huge_val();
     double M[4];
@@ -711,20 +724,24 @@ __device__ __forceinline__ void maxplus_product(int first, int last, int T, doub
     for (int jj = 0; jj < 4; ++jj) M[jj] = (r == 4 * q + jj) ? 0.0 : ninf;
     Slot ring[PF];
     auto load = [&](int i, int slot) { load_slot(i, ring[slot]); };
+    int buf = 0;
     walk<PF>(first, last, +1, load, [&](int, int slot) {
-        __syncthreads();
+        buf ^= 1;
+        XT(*X)[16] = Xs[buf];
 #pragma unroll
-        for (int jj = 0; jj < 4; ++jj) {
-            Xs[r][4 * q + jj] = get(ring[slot], jj);
-            Mc[r][4 * q + jj] = M[jj];
-        }
+        for (int jj = 0; jj < 4; ++jj) X[r][4 * q + jj] = get(ring[slot], jj);
         __syncthreads();
         double best[4] = {ninf, ninf, ninf, ninf};
+        const auto row = [&](int s, double m) {
 #pragma unroll
-        for (int s = 0; s < 16; ++s) {
-            const double m = Mc[r][s];
+            for (int jj = 0; jj < 4; ++jj) best[jj] = fmax(best[jj], m + (double)X[s][4 * q + jj]);
+        };
 #pragma unroll
-            for (int jj = 0; jj < 4; ++jj) best[jj] = fmax(best[jj], m + Xs[s][4 * q + jj]);
+        for (int jj = 0; jj < 4; ++jj) {
+            row(jj, quad_read<0>(M[jj]));
+            row(4 + jj, quad_read<1>(M[jj]));
+            row(8 + jj, quad_read<2>(M[jj]));
+            row(12 + jj, quad_read<3>(M[jj]));
         }
 #pragma unroll
         for (int jj = 0; jj < 4; ++jj) M[jj] = best[jj];
@@ -738,8 +755,7 @@ struct MaxSlotD { double x[4]; };
 
 template <typename TIN>
 __global__ __launch_bounds__(64) void chunk_maxplus_kernel(MaxScanArgs a) {
-    __shared__ __attribute__((aligned(16))) double Mc[16][18];
-    __shared__ __attribute__((aligned(16))) double Xs[16][16];
+    __shared__ __attribute__((aligned(16))) float Xs[2][16][16];
     const int lane = threadIdx.x, r = lane >> 2, q = lane & 3;
     const int b = blockIdx.x / a.C, c = blockIdx.x % a.C;
     const int T = a.T, N = a.N;
@@ -757,20 +773,19 @@ __global__ __launch_bounds__(64) void chunk_maxplus_kernel(MaxScanArgs a) {
         in[jj] = r < T && t < T;
         off[jj] = (r < T ? r : T - 1) * T + (t < T ? t : T - 1);
     }
-    maxplus_product<kScanPF, MaxSlotF>(
+    maxplus_product<kScanPF, MaxSlotF, float>(
         first, last, T, a.Mx + ((size_t)b * a.C + c) * 256,
         [&](int i, MaxSlotF& sl) {
             const TIN* m = phib + (size_t)i * TT;
 #pragma unroll
             for (int jj = 0; jj < 4; ++jj) sl.x[jj] = Elem<TIN>::get(m + off[jj]);
         },
-        [&](const MaxSlotF& sl, int jj) { return in[jj] ? (double)sl.x[jj] : -__builtin_huge_val(); }, Mc, Xs);
+        [&](const MaxSlotF& sl, int jj) { return in[jj] ? sl.x[jj] : LCCRF_NEG_INF; }, Xs);
 }
 
 // One wave per group of GS chunks: the max-plus product of the group's chunk matrices.
 __global__ __launch_bounds__(64) void group_maxplus_kernel(MaxScanArgs a) {
-    __shared__ __attribute__((aligned(16))) double Mc[16][18];
-    __shared__ __attribute__((aligned(16))) double Xs[16][16];
+    __shared__ __attribute__((aligned(16))) double Xs[2][16][16];
     const int lane = threadIdx.x, r = lane >> 2, q = lane & 3;
     const int b = blockIdx.x / a.G, g = blockIdx.x % a.G;
     const int L = clamp_length(a.lengths, b, a.N);
@@ -779,13 +794,13 @@ __global__ __launch_bounds__(64) void group_maxplus_kernel(MaxScanArgs a) {
     if (c0 >= Cb) return;
     const int c1 = (c0 + a.GS < Cb ? c0 + a.GS : Cb) - 1;
     const double* Mb = a.Mx + (size_t)b * a.C * 256 + r * 16 + 4 * q;
-    maxplus_product<4, MaxSlotD>(
+    maxplus_product<4, MaxSlotD, double>(
         c0, c1, a.T, a.Mx2 + ((size_t)b * a.G + g) * 256,
         [&](int c, MaxSlotD& sl) {
 #pragma unroll
             for (int jj = 0; jj < 4; ++jj) sl.x[jj] = Mb[(size_t)c * 256 + jj];
         },
-        [&](const MaxSlotD& sl, int jj) { return sl.x[jj]; }, Mc, Xs);
+        [&](const MaxSlotD& sl, int jj) { return sl.x[jj]; }, Xs);
 }
 
 constexpr int kPinWindow = 1024;  // chunks of back-pointers held in LDS at a time by the back-trace
