@@ -342,6 +342,32 @@ static int cross_query(bool kl, const void* phi_p, const void* phi_q, lccrf_dtyp
     hipStream_t st = static_cast<hipStream_t>(stream);
     // log Z_q first: the chains of p then reuse the vectors' storage, the double-precision result stays
     hipError_t e = launch_log_partition64(phi_q, dt, lengths, B, N, T, w, base, st);
+    if (scan_pays(B, N, T) || (scan_pays_sum(B, N, T) && N >= 16 * g_scan_chunk)) {
+        // Long chains over few tags: the chains of p under the chunked scan, as for the entropy; the second
+        // pass adds up the expectation of phi_q (of phi_q - phi_p) edge by edge from the marginals of p it
+        // forms in registers.
+        float* Fv = reinterpret_cast<float*>(base + w.Fv);
+        double* OF = reinterpret_cast<double*>(base + w.OF);
+        float* Gv = reinterpret_cast<float*>(base + w.Gv);
+        double* OG = reinterpret_cast<double*>(base + w.OG);
+        float* ent = reinterpret_cast<float*>(base + w.ent);
+        double* lzp = reinterpret_cast<double*>(base + w.hoff);
+        if (e == hipSuccess)
+            e = lccrf::launch_scan_boundaries(dt, phi_p, lengths, B, N, T, g_scan_chunk,
+                                              reinterpret_cast<float*>(base + w.Pl), reinterpret_cast<float*>(base + w.rel),
+                                              reinterpret_cast<double*>(base + w.base), Fv, OF, Gv, OG,
+                                              group_buffers(w, base), nullptr, true, st, lzp);
+        if (e == hipSuccess)
+            e = lccrf::launch_chunked_marginals(dt, phi_p, lengths, B, N, T, reinterpret_cast<float*>(base + w.ua),
+                                                reinterpret_cast<float*>(base + w.ub),
+                                                reinterpret_cast<double*>(base + w.Oa),
+                                                reinterpret_cast<double*>(base + w.Ob), nullptr, g_scan_chunk, Fv, OF,
+                                                Gv, OG, st, nullptr, false, ent, phi_q, kl);
+        if (e == hipSuccess)
+            e = lccrf::launch_cross_reduce(kl, ent, lengths, reinterpret_cast<const double*>(base + w.lz64), lzp, B, N,
+                                           g_scan_chunk, out, st);
+        return e == hipSuccess ? LCCRF_OK : LCCRF_ELAUNCH;
+    }
     if (e == hipSuccess)
         e = lccrf::launch_cross(kl, dt, phi_p, phi_q, lengths, B, N, T, reinterpret_cast<float*>(base + w.ua),
                                 reinterpret_cast<float*>(base + w.ub), reinterpret_cast<double*>(base + w.Oa),

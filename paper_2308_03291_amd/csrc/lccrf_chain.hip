@@ -969,10 +969,13 @@ hipError_t launch_sequential_sum(int op, int dtype, const void* phi, const int32
 hipError_t launch_chunked_marginals(int dtype, const void* phi, const int32_t* lengths, int B, int N, int T,
                                     float* ua, float* ub, double* Oa, double* Ob, float* mu, int chunk,
                                     const float* Fv, const double* OF, const float* Gv, const double* OG,
-                                    hipStream_t st, hipEvent_t between, bool exact_only, float* ent) {
+                                    hipStream_t st, hipEvent_t between, bool exact_only, float* ent, const void* psi,
+                                    bool difference) {
     const int C = (N + chunk - 1) / chunk;
     ChainArgs a{phi, lengths, B, N, T, ua, ub, Oa, Ob, nullptr, mu, exact_only ? 1 : 0, nullptr, chunk, C, Fv, OF, Gv, OG};
-    a.ent = ent;  // entropy mode of the second pass (one-wave kernels only: the scan's tag sets)
+    a.ent = ent;  // entropy or expectation mode of the second pass (one-wave kernels only: the scan's tag sets)
+    a.ent_kind = !ent ? 0 : !psi ? 1 : difference ? 3 : 2;
+    if (ent) a.psi = psi;  // (only the second pass of the one-wave kernels looks at it)
     if (ent && !wave_supported(T)) return hipErrorInvalidValue;
     if (wave_supported(T)) return launch_wave(1, dtype, a, st, between);
     const PairPlan pair{nullptr, nullptr, dtype};

@@ -43,6 +43,9 @@ struct ChainArgs {
     // Entropy by edges (ent non-null, second pass of the one-wave kernels): no marginals are written, every
     // wave leaves the summed conditional entropies of its edges (base 2) in ent[2 (b C + c) + dir].
     float* ent;
+    // What ent receives: 0 or 1 the entropy; 2 the expectation of the potentials psi under this chain's
+    // marginals, sum_e mu(e) psi(e), in natural units; 3 that of psi - phi.
+    int ent_kind;
     // Structured potentials (emit non-null; float only, T <= 64, whole sequences): phi is not read,
     // phi[b][i][s][t] = trans[s][t] + emit[b][i][t].
     const float* emit;   // [B][N][T]

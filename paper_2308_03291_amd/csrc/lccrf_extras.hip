@@ -412,6 +412,36 @@ hipError_t launch_entropy_reduce(const float* ent, const int32_t* lengths, const
     return hipGetLastError();
 }
 
+// The same sum over the chunks for the expectations of a second chain's potentials (natural units):
+// cross-entropy logZq - E, or with kl the divergence logZq - logZp - E for E the expectation of the
+// difference of the potentials.  No finite path under the chain itself (logZp = -inf): NaN.
+__global__ __launch_bounds__(64) void cross_reduce_kernel(const float* __restrict__ ent, const int32_t* __restrict__ lengths,
+                                                          const double* __restrict__ logZq, const double* __restrict__ logZp,
+                                                          int N, int chunk, int C, int kl, float* __restrict__ out) {
+    const int b = blockIdx.x, lane = threadIdx.x;
+    const int L = clamp_length(lengths, b, N);
+    if (L == 0) {
+        if (lane == 0) out[b] = 0.f;
+        return;
+    }
+    const int Cb = (L + chunk - 1) / chunk;
+    double acc = 0.0;
+    for (int k = lane; k < 2 * Cb; k += 64) acc += (double)ent[2 * (size_t)b * C + k];
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) acc += __shfl_xor(acc, off, 64);
+    if (lane == 0) {
+        const double lzp = logZp[b];
+        out[b] = lzp == -__builtin_huge_val() ? __builtin_nanf("") : (float)(logZq[b] - (kl ? lzp : 0.0) - acc);
+    }
+}
+
+hipError_t launch_cross_reduce(bool kl, const float* ent, const int32_t* lengths, const double* logZq, const double* logZp,
+                               int B, int N, int chunk, float* out, hipStream_t st) {
+    const int C = (N + chunk - 1) / chunk;
+    hipLaunchKernelGGL(cross_reduce_kernel, dim3(B), dim3(64), 0, st, ent, lengths, logZq, logZp, N, chunk, C, kl ? 1 : 0, out);
+    return hipGetLastError();
+}
+
 // Cross-entropy H(p, q) = log Z_q - E_p[score_q(y)] (kl = false) or Kullback-Leibler divergence
 // KL(p || q) = E_p[score_p(y) - score_q(y)] - log Z_p + log Z_q (kl = true) of two chains over the
 // same sequences: the expectation from the half chains of p at their meeting position (as the

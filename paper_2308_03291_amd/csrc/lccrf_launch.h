@@ -72,12 +72,20 @@ hipError_t launch_path_log_prob(int dtype, const void* phi, const int32_t* lengt
 hipError_t launch_chunked_marginals(int dtype, const void* phi, const int32_t* lengths, int B, int N, int T,
                                     float* ua, float* ub, double* Oa, double* Ob, float* mu, int chunk,
                                     const float* Fv, const double* OF, const float* Gv, const double* OG,
-                                    hipStream_t st, hipEvent_t between, bool exact_only, float* ent = nullptr);
+                                    hipStream_t st, hipEvent_t between, bool exact_only, float* ent = nullptr,
+                                    const void* psi = nullptr, bool difference = false);
 // ent non-null (T <= 32): the second pass writes no marginals (mu may be null) but the summed conditional
 // entropies of every chunk's edges, [B][C][2] floats (base 2); launch_entropy_reduce adds them up to H [B].
 // logZ: [B] floats from the boundary pass of the same run (-inf: no finite path, H is NaN).
 hipError_t launch_entropy_reduce(const float* ent, const int32_t* lengths, const float* logZ, int B, int N, int chunk,
                                  float* H, hipStream_t st);
+// ent and psi non-null: ent receives the expectation of the potentials psi (same layout and type as phi) under
+// the chain of phi instead, sum_e mu(e) psi(e) over every chunk's edges in natural units, or that of psi - phi
+// (difference).  launch_cross_reduce turns the sums into the cross-entropy logZq - E (logZp = the chain's own
+// log-partition, only looked at for -inf: no finite path, NaN) or, with kl, into the Kullback-Leibler
+// divergence logZq - logZp - E of the difference; both log-partitions [B] doubles, natural logarithm.
+hipError_t launch_cross_reduce(bool kl, const float* ent, const int32_t* lengths, const double* logZq, const double* logZp,
+                               int B, int N, int chunk, float* out, hipStream_t st);
 
 // Max-plus chains (two per sequence, meeting in the middle) and the trace.  bp: [B][N][T] bytes,
 // mid: viterbi_mid_doubles(B, 1, T) doubles of scratch.

@@ -102,14 +102,17 @@ __device__ __forceinline__ float max4(const float (&x)[4]) { return fmaxf(fmaxf(
 // computed as U(t) / S(t) + log2 S(t) with U(t) = sum_s e(s,t) [h(s) - log2 e(s,t)] for the same
 // shifted exponentials e the step already forms (hin in row form, hout in column form).
 
-// With ENT (and WITH_MU) the marginals mu_i(s,t) are not stored: the step adds the conditional entropy
+// With ENT = 1 (and WITH_MU) the marginals mu_i(s,t) are not stored: the step adds the conditional entropy
 // of the edge, H(y_i | y_{i-1}) = sum_s m(s) log2 m(s) - sum_{s,t} mu log2 mu with m(s) = sum_t mu_i(s,t)
 // (base 2, every term in the lane that holds it; the caller sums hacc over the wave at the end).
-template <int TP, bool WITH_MU, bool ALIGNED, bool WITH_H = false, bool ENT = false>
+// ENT = 2: neither are they stored; the step adds sum_{s,t} mu_i(s,t) wt(s,t) for the weights wt handed in
+// (natural units: the expectation of a second chain's potentials under this chain).
+template <int TP, bool WITH_MU, bool ALIGNED, bool WITH_H = false, int ENT = 0>
 __device__ __forceinline__ void wave_fwd_step(float (&v)[WGeo<TP>::R][4], const float (&ua)[WGeo<TP>::R], float c,
                                               const float (&ubK)[4], float* __restrict__ mu_out, int T, int lane,
                                               bool exact_only, float (&r)[4], float& tot,
-                                              const float (&hin)[WGeo<TP>::R], float (&hout)[4], float& hacc) {
+                                              const float (&hin)[WGeo<TP>::R], float (&hout)[4], float& hacc,
+                                              const float (*wt)[4] = nullptr) {
     using W = WGeo<TP>;
     constexpr int R = W::R;
     const int c4 = 4 * (lane % W::CG), s0 = R * (lane / W::CG);
@@ -134,16 +137,20 @@ __device__ __forceinline__ void wave_fwd_step(float (&v)[WGeo<TP>::R][4], const 
                 e[j] = ex2(arg);
                 ls[j] += e[j];
                 if (WITH_H) lu[j] = __builtin_fmaf(e[j], hin[k] - log2_term(arg), lu[j]);
-                if (ENT) {
+                if (ENT == 1) {
                     const float w = e[j] * gm[j];
                     rowl += w;
                     hstep -= w > 0.f ? w * (arg + lgm[j]) : 0.f;
                 }
+                if (ENT == 2) {
+                    const float w = e[j] * gm[j];
+                    hstep += w > 0.f ? w * wt[k][j] : 0.f;
+                }
             }
-            if (ENT) {
+            if (ENT == 1) {
                 const float m = xor_sum<1, W::CG>(rowl);
                 hstep += (c4 == 0 && m > 0.f) ? m * lg2(m) : 0.f;
-            } else if (WITH_MU) {
+            } else if (ENT == 0 && WITH_MU) {
                 store4<ALIGNED>(mu_out, T, s0 + k, c4, e[0] * gm[0], e[1] * gm[1], e[2] * gm[2], e[3] * gm[3]);
             }
         }
@@ -159,7 +166,7 @@ __device__ __forceinline__ void wave_fwd_step(float (&v)[WGeo<TP>::R][4], const 
         }
         accepted = __builtin_amdgcn_ballot_w64(!ok) == 0;
         if (WITH_MU && accepted) tot = xor_sum<1, 64>(part);
-        if (ENT && accepted) hacc += hstep;
+        if (ENT != 0 && accepted) hacc += hstep;
     }
     if (!accepted) {
         float lm[4] = {LCCRF_NEG_INF, LCCRF_NEG_INF, LCCRF_NEG_INF, LCCRF_NEG_INF};
@@ -190,16 +197,20 @@ __device__ __forceinline__ void wave_fwd_step(float (&v)[WGeo<TP>::R][4], const 
                 e[j] = ex2(arg);
                 ls[j] += e[j];
                 if (WITH_H) lu[j] = __builtin_fmaf(e[j], hin[k] - log2_term(arg), lu[j]);
-                if (ENT) {
+                if (ENT == 1) {
                     const float w = e[j] * gm[j];
                     rowl += w;
                     hacc -= w > 0.f ? w * (arg + lgm[j]) : 0.f;
                 }
+                if (ENT == 2) {
+                    const float w = e[j] * gm[j];
+                    hacc += w > 0.f ? w * wt[k][j] : 0.f;
+                }
             }
-            if (ENT) {
+            if (ENT == 1) {
                 const float m = xor_sum<1, W::CG>(rowl);
                 hacc += (c4 == 0 && m > 0.f) ? m * lg2(m) : 0.f;
-            } else if (WITH_MU) {
+            } else if (ENT == 0 && WITH_MU) {
                 store4<ALIGNED>(mu_out, T, s0 + k, c4, e[0] * gm[0], e[1] * gm[1], e[2] * gm[2], e[3] * gm[3]);
             }
         }
@@ -216,11 +227,12 @@ __device__ __forceinline__ void wave_fwd_step(float (&v)[WGeo<TP>::R][4], const 
 // One backward position: r(s) = log2 sum_t 2^(phi2(s,t) + ub(t)), ub in column form, r in row form.
 // WITH_H: the conditional entropy of the path ahead of the current tag (hin in column form, hout in row form).
 // ENT as in wave_fwd_step; here m(s) = S(s) f(s) and the factor f(s) of row s drops out of log2 (mu / m).
-template <int TP, bool WITH_MU, bool ALIGNED, bool WITH_H = false, bool ENT = false>
+template <int TP, bool WITH_MU, bool ALIGNED, bool WITH_H = false, int ENT = 0>
 __device__ __forceinline__ void wave_bwd_step(float (&v)[WGeo<TP>::R][4], const float (&ub)[4], float c,
                                               const float (&uaK)[WGeo<TP>::R], float* __restrict__ mu_out, int T,
                                               int lane, bool exact_only, float (&r)[WGeo<TP>::R], float& tot,
-                                              const float (&hin)[4], float (&hout)[WGeo<TP>::R], float& hacc) {
+                                              const float (&hin)[4], float (&hout)[WGeo<TP>::R], float& hacc,
+                                              const float (*wt)[4] = nullptr) {
     using W = WGeo<TP>;
     constexpr int R = W::R;
     const int c4 = 4 * (lane % W::CG), s0 = R * (lane / W::CG);
@@ -237,13 +249,15 @@ __device__ __forceinline__ void wave_bwd_step(float (&v)[WGeo<TP>::R][4], const 
                 const float arg = __builtin_fmaf(v[k][j], kLog2e, ubc[j]);
                 e[j] = ex2(arg);
                 if (WITH_H) Ul = __builtin_fmaf(e[j], hin[j] - log2_term(arg), Ul);
-                if (ENT) El += e[j] > 0.f ? e[j] * arg : 0.f;
+                if (ENT == 1) El += e[j] > 0.f ? e[j] * arg : 0.f;
+                if (ENT == 2) El += e[j] > 0.f ? e[j] * wt[k][j] : 0.f;
             }
             const float Sl = (e[0] + e[1]) + (e[2] + e[3]);
             const float S = xor_sum<1, W::CG>(Sl);
             if (WITH_MU) {
                 const float f = ex2(c + uaK[k]);
-                if (ENT) hstep += f > 0.f ? f * (((c4 == 0 && S > 0.f) ? S * lg2(S) : 0.f) - El) : 0.f;
+                if (ENT == 1) hstep += f > 0.f ? f * (((c4 == 0 && S > 0.f) ? S * lg2(S) : 0.f) - El) : 0.f;
+                else if (ENT == 2) hstep += f > 0.f ? f * El : 0.f;
                 else store4<ALIGNED>(mu_out, T, s0 + k, c4, e[0] * f, e[1] * f, e[2] * f, e[3] * f);
                 part += Sl * f;
             }
@@ -254,7 +268,7 @@ __device__ __forceinline__ void wave_bwd_step(float (&v)[WGeo<TP>::R][4], const 
         }
         accepted = __builtin_amdgcn_ballot_w64(!ok) == 0;
         if (WITH_MU && accepted) tot = xor_sum<1, 64>(part);
-        if (ENT && accepted) hacc += hstep;
+        if (ENT != 0 && accepted) hacc += hstep;
     }
     if (!accepted) {
         float part = 0.f;
@@ -270,13 +284,15 @@ __device__ __forceinline__ void wave_bwd_step(float (&v)[WGeo<TP>::R][4], const 
                 const float arg = v[k][j] - g;
                 e[j] = ex2(arg);
                 if (WITH_H) Ul = __builtin_fmaf(e[j], hin[j] - log2_term(arg), Ul);
-                if (ENT) El += e[j] > 0.f ? e[j] * arg : 0.f;
+                if (ENT == 1) El += e[j] > 0.f ? e[j] * arg : 0.f;
+                if (ENT == 2) El += e[j] > 0.f ? e[j] * wt[k][j] : 0.f;
             }
             const float Sl = (e[0] + e[1]) + (e[2] + e[3]);
             const float S = xor_sum<1, W::CG>(Sl);
             if (WITH_MU) {
                 const float f = ex2(g + uaK[k]);
-                if (ENT) hacc += f > 0.f ? f * (((c4 == 0 && S > 0.f) ? S * lg2(S) : 0.f) - El) : 0.f;
+                if (ENT == 1) hacc += f > 0.f ? f * (((c4 == 0 && S > 0.f) ? S * lg2(S) : 0.f) - El) : 0.f;
+                else if (ENT == 2) hacc += f > 0.f ? f * El : 0.f;
                 else store4<ALIGNED>(mu_out, T, s0 + k, c4, e[0] * f, e[1] * f, e[2] * f, e[3] * f);
                 part += Sl * f;
             }
@@ -419,7 +435,9 @@ __global__ __launch_bounds__(64) void wave_half_kernel(ChainArgs a) {
 // ENT: no marginal is written; every wave adds up the conditional entropies H(y_i | y_{i-1}) of its
 // edges (the wave of position 0 also H(y_0)) and leaves the sum, base 2, in a.ent[2 (b C + c) + dir]:
 // by the chain rule their total is the entropy of the sequence.
-template <int TP, typename TIN, bool ALIGNED, bool STRUCT, bool ENT = false>
+// ENT = 2: the same with the expectation of a second chain's potentials a.psi under this chain's
+// marginals, sum_e mu(e) psi(e) (a.ent_kind = 2), or of psi - phi (a.ent_kind = 3), in natural units.
+template <int TP, typename TIN, bool ALIGNED, bool STRUCT, int ENT = 0>
 __global__ __launch_bounds__(64) void wave_marginal_kernel(ChainArgs a) {
     using W = WGeo<TP>;
     constexpr int R = W::R, PF = wave_ring_depth(TP, true);
@@ -428,11 +446,11 @@ __global__ __launch_bounds__(64) void wave_marginal_kernel(ChainArgs a) {
     const Span sp = make_span(a, blockIdx.x >> 1);
     const int b = sp.b, N = a.N, T = a.T, L = sp.L;
     const size_t TT = (size_t)T * T, vb = (size_t)b * N;
-    float* mub = ENT ? nullptr : a.mu + (size_t)b * N * TT;
+    float* mub = ENT != 0 ? nullptr : a.mu + (size_t)b * N * TT;
     const bool exact_only = a.exact_only != 0;
     float hacc = 0.f;
 
-    if (!ENT && dir == 0) {
+    if (ENT == 0 && dir == 0) {
         // positions past the end carry no edge: their marginals are zero (a chunk clears its own range)
         const int zfrom = a.chunk > 0 ? (sp.c * a.chunk > L ? sp.c * a.chunk : L) : L;
         const int zto = a.chunk > 0 ? ((sp.c + 1) * a.chunk < N ? (sp.c + 1) * a.chunk : N) : N;
@@ -472,12 +490,27 @@ __global__ __launch_bounds__(64) void wave_marginal_kernel(ChainArgs a) {
 
     float ring[PF][R][4];
     constexpr bool structured = STRUCT;
+    static_assert(!(STRUCT && ENT == 2), "no expectations over structured potentials");
     const float* emb = structured ? a.emit + (size_t)b * N * T : nullptr;
     float tr[R][4];
     if constexpr (structured) wave_load<TP, float, ALIGNED>(a.trans, T, lane, tr);
+    const TIN* psib = ENT == 2 ? static_cast<const TIN*>(a.psi) + (size_t)b * N * TT : nullptr;
+    const bool difference = a.ent_kind == 3;
+    float ringq[ENT == 2 ? PF : 1][R][4];
     auto load_phi = [&](int i, int slot) {
         if constexpr (structured) wave_load_emit<TP, ALIGNED>(emb + (size_t)i * T, T, lane, ring[slot]);
         else wave_load<TP, TIN, ALIGNED>(phib + (size_t)i * TT, T, lane, ring[slot]);
+        if constexpr (ENT == 2) wave_load<TP, TIN, ALIGNED>(psib + (size_t)i * TT, T, lane, ringq[slot]);
+    };
+    // the weights of the expectation for the tile in `slot` (before the step rewrites the tile)
+    float wt[R][4];
+    auto weights = [&](int slot) {
+        if constexpr (ENT == 2) {
+#pragma unroll
+            for (int k = 0; k < R; ++k)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) wt[k][j] = difference ? ringq[slot][k][j] - ring[slot][k][j] : ringq[slot][k][j];
+        }
     };
     float kappa = 0.f, tot = 0.f;
     float noh_c[4] = {0.f, 0.f, 0.f, 0.f}, noh_r[R];  // no entropy carried in this pass
@@ -510,7 +543,8 @@ __global__ __launch_bounds__(64) void wave_marginal_kernel(ChainArgs a) {
             float ubK[4];
 #pragma unroll
             for (int j = 0; j < 4; ++j) ubK[j] = (c4 + j < T) ? aux[slot][j] + K : LCCRF_NEG_INF;
-            wave_fwd_step<TP, true, ALIGNED, false, ENT>(ring[slot], ua, d, ubK, ENT ? nullptr : mub + (size_t)i * TT, T, lane, exact_only, vc, tot, noh_r, noh_c, hacc);
+            weights(slot);
+            wave_fwd_step<TP, true, ALIGNED, false, ENT>(ring[slot], ua, d, ubK, ENT != 0 ? nullptr : mub + (size_t)i * TT, T, lane, exact_only, vc, tot, noh_r, noh_c, hacc, wt);
         });
     } else {
         double O = a.Ob[vb + h];
@@ -541,17 +575,18 @@ __global__ __launch_bounds__(64) void wave_marginal_kernel(ChainArgs a) {
             float uaK[R];
 #pragma unroll
             for (int k = 0; k < R; ++k) uaK[k] = (s0 + k < T) ? aux[slot][k] + K : LCCRF_NEG_INF;
-            wave_bwd_step<TP, true, ALIGNED, false, ENT>(ring[slot], ub, d, uaK, ENT ? nullptr : mub + (size_t)i * TT, T, lane, exact_only, vr, tot, noh_c, noh_r, hacc);
+            weights(slot);
+            wave_bwd_step<TP, true, ALIGNED, false, ENT>(ring[slot], ub, d, uaK, ENT != 0 ? nullptr : mub + (size_t)i * TT, T, lane, exact_only, vr, tot, noh_c, noh_r, hacc, wt);
         });
         // position 0: p(y_0 = t) = softmax_t(alpha_0(t) + beta_0(t)) in row 0, zeros elsewhere
         if (!sp.first) {
-            if (ENT) {
+            if (ENT != 0) {
                 hacc = xor_sum<1, 64>(hacc);
                 if (lane == 0) a.ent[2 * ((size_t)b * a.C + sp.c) + 1] = hacc;
             }
             return;
         }
-        if (!ENT)
+        if (ENT == 0)
             for (int k = T + lane; k < (int)TT; k += 64) mub[k] = 0.f;
         float z[R], m = LCCRF_NEG_INF;
 #pragma unroll
@@ -570,12 +605,18 @@ __global__ __launch_bounds__(64) void wave_marginal_kernel(ChainArgs a) {
             for (int k = 0; k < R; ++k) {
                 if (s0 + k >= T) continue;
                 const float p = cnorm * ex2(z[k] - m);
-                if (ENT) hacc -= p > 0.f ? p * (z[k] - m - lg2(S)) : 0.f;  // H(y_0)
-                else mub[s0 + k] = p;
+                if (ENT == 1) {
+                    hacc -= p > 0.f ? p * (z[k] - m - lg2(S)) : 0.f;  // H(y_0)
+                } else if (ENT == 2) {  // the first row of the first matrix
+                    const float q0 = Elem<TIN>::get(psib + s0 + k);
+                    hacc += p > 0.f ? p * (difference ? q0 - Elem<TIN>::get(phib + s0 + k) : q0) : 0.f;
+                } else {
+                    mub[s0 + k] = p;
+                }
             }
         }
     }
-    if (ENT) {
+    if (ENT != 0) {
         hacc = xor_sum<1, 64>(hacc);
         if (lane == 0) a.ent[2 * ((size_t)b * a.C + sp.c) + dir] = hacc;
     }
@@ -596,8 +637,10 @@ static hipError_t launch_wave_tp(bool second_pass, const ChainArgs& a, hipStream
             return hipGetLastError();
         }
     }
-    if (second_pass && a.ent)
-        hipLaunchKernelGGL((wave_marginal_kernel<TP, TIN, ALIGNED, false, true>), grid, dim3(64), 0, st, a);
+    if (second_pass && a.ent && a.ent_kind >= 2)
+        hipLaunchKernelGGL((wave_marginal_kernel<TP, TIN, ALIGNED, false, 2>), grid, dim3(64), 0, st, a);
+    else if (second_pass && a.ent)
+        hipLaunchKernelGGL((wave_marginal_kernel<TP, TIN, ALIGNED, false, 1>), grid, dim3(64), 0, st, a);
     else if (second_pass)
         hipLaunchKernelGGL((wave_marginal_kernel<TP, TIN, ALIGNED, false>), grid, dim3(64), 0, st, a);
     else if (a.ha)

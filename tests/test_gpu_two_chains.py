@@ -86,6 +86,33 @@ def test_two_chains_bf16_peaked_and_forbidden_edges(crf, oracle_mod, T):
     _check(crf, oracle_mod, p, q, None, f"-inf T={T}")
 
 
+@pytest.mark.parametrize("T,N,k", [(3, 70, 4), (16, 130, 8), (16, 1100, 16), (13, 300, 8), (24, 300, 8), (32, 530, 32)])
+def test_two_chains_under_the_scan(crf, oracle_mod, T, N, k):
+    """Long chains over few tags take the chunked scan: the expectation is then added up edge by edge
+    in every chunk.  Small chunks so that short inputs cover many chunks, ragged and empty sequences,
+    peaked bf16 potentials, forbidden edges, a chain without a finite path."""
+    crf.set_scan_chunk(k)
+    try:
+        p, q, lens = _pair(7400 + 13 * T + N, 6, N, T, ragged=True, min_len=0)
+        lens[0], lens[1] = N, 0
+        _check(crf, oracle_mod, p, q, lens, f"scan T={T} N={N} chunk {k}")
+        p, q, lens = _pair(7500 + 13 * T + N, 3, N, T, scale_p=6.0, scale_q=3.0, dtype="bf16", ragged=True, min_len=N // 2)
+        _check(crf, oracle_mod, p, q, lens, f"scan peaked bf16 T={T} N={N} chunk {k}")
+        if T >= 8:
+            p, q, _ = _pair(7600 + 13 * T + N, 4, N, T)
+            ninf = float("-inf")
+            p[0, :, 3, :] = ninf
+            q[0, 5, 3, :] = ninf
+            q[1, 10, :, 5] = ninf
+            p[2, 12, :, :] = ninf
+            mask = torch.rand(N, T, T, generator=torch.Generator().manual_seed(7)) < 0.5
+            p[3][mask] = ninf
+            p[3, :, torch.arange(T), torch.arange(T)] = 0.0
+            _check(crf, oracle_mod, p, q, None, f"scan -inf T={T} N={N} chunk {k}")
+    finally:
+        crf.set_scan_chunk(0)
+
+
 @pytest.mark.parametrize("key", ["cfg1", "cfg2", "cfg3", "cfg5"])
 def test_two_chains_named_workloads(crf, oracle_mod, key):
     w = workloads.WORKLOADS[key]
