@@ -7,6 +7,7 @@ import torch
 
 from paper_2308_03291_amd import workloads
 from test_gpu_parity import check_case, crf  # noqa: F401  (fixture)
+from test_gpu_two_chains import _check as check_two_chains
 
 pytestmark = pytest.mark.gpu
 
@@ -42,5 +43,8 @@ def test_random_shape(crf, oracle_mod, k, B, N, T, scale, dtype, ragged, chunk):
         H = crf.lccrf_entropy(phi.cuda(), dl).cpu().numpy().astype(np.float64)
         want = oracle_mod.entropy(phi, lens_np)
         assert np.all(np.abs(H - want) <= 2e-4 * np.maximum(1.0, np.abs(want))), f"{what}: entropy {H} vs {want}"
+        if k % 3 == 0:   # a second chain over the same sequences: cross-entropy and KL divergence
+            q, _ = workloads.random_case(80000 + k, B, N, T, scale=0.5 * scale, dtype=dtype)
+            check_two_chains(crf, oracle_mod, phi, q, lens if ragged else None, what)
     finally:
         crf.set_scan_chunk(0)
