@@ -240,191 +240,189 @@ __device__ __forceinline__ bool linear_product(const Src& src, int first, int la
     using vec = typename L::vec;
     constexpr int NB = S::NB, NE = S::NE;
     const int lane = threadIdx.x;
-    {
-        const int g = lane >> 4, j = lane & 15;
-        unsigned in = 0;
+    const int g = lane >> 4, j = lane & 15;
+    unsigned in = 0;
 #pragma unroll
-        for (int e = 0; e < NE; ++e) in |= (S::row(lane, e) < T && S::col(lane, e) < T) ? (1u << e) : 0u;
-        // The zero pattern of D (1 where some path exists) is carried along by a product of 0/1
-        // matrices on the f32 MFMA, from the first matrix with a -inf entry on (until then D is
-        // the identity or has no zero).  That instruction numbers its output rows 4g + v; beside the
-        // f64 product it therefore runs on rows renamed by pi(4g + v) = g + 4v: its A operand is the
-        // flag of column pi(j).
-        const int pj = F64 ? ((lane & 48) | (4 * (j & 3) + (j >> 2))) : lane;
-        scalar D[NB][NB][4];
-        float Z[NB][NB][4];
-        double Msum = 0.0;
-        int esum[NB];
-        bool bad = false, tracking = false, started = false, rejected = false;
+    for (int e = 0; e < NE; ++e) in |= (S::row(lane, e) < T && S::col(lane, e) < T) ? (1u << e) : 0u;
+    // The zero pattern of D (1 where some path exists) is carried along by a product of 0/1
+    // matrices on the f32 MFMA, from the first matrix with a -inf entry on (until then D is
+    // the identity or has no zero).  That instruction numbers its output rows 4g + v; beside the
+    // f64 product it therefore runs on rows renamed by pi(4g + v) = g + 4v: its A operand is the
+    // flag of column pi(j).
+    const int pj = F64 ? ((lane & 48) | (4 * (j & 3) + (j >> 2))) : lane;
+    scalar D[NB][NB][4];
+    float Z[NB][NB][4];
+    double Msum = 0.0;
+    int esum[NB];
+    bool bad = false, tracking = false, started = false, rejected = false;
+#pragma unroll
+    for (int sb = 0; sb < NB; ++sb)
+#pragma unroll
+        for (int rb = 0; rb < NB; ++rb)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const bool diag = sb == rb && (F64 ? g + 4 * v : 4 * g + v) == j;
+                D[sb][rb][v] = diag ? (scalar)1 : (scalar)0;
+                Z[sb][rb][v] = diag ? 1.f : 0.f;
+            }
+#pragma unroll
+    for (int rb = 0; rb < NB; ++rb) esum[rb] = 0;
+    typename Src::Slot ring[Src::PF];
+    auto load = [&](int i, int slot) { src.load(i, ring[slot]); };
+    // The single-precision product looks at every position whether it still holds, and ends at
+    // once if not; the double-precision one hardly ever fails and is judged at the end.
+    const auto step = [&](int, int slot) -> bool {
+        float x[NE];
+        const double common = src.entries(ring[slot], x);
+        float mloc = x[0];
+#pragma unroll
+        for (int e = 1; e < NE; ++e) mloc = fmaxf(mloc, x[e]);
+        const float m = finite_or_zero(xor_max<1, 64>(mloc));
+        Msum += (double)m + common;
+        vec acc[NB][NB];
+#pragma unroll
+        for (int tb = 0; tb < NB; ++tb)
+#pragma unroll
+            for (int rb = 0; rb < NB; ++rb) acc[tb][rb] = vec{0, 0, 0, 0};
 #pragma unroll
         for (int sb = 0; sb < NB; ++sb)
 #pragma unroll
-            for (int rb = 0; rb < NB; ++rb)
+            for (int tb = 0; tb < NB; ++tb)
 #pragma unroll
                 for (int v = 0; v < 4; ++v) {
-                    const bool diag = sb == rb && (F64 ? g + 4 * v : 4 * g + v) == j;
-                    D[sb][rb][v] = diag ? (scalar)1 : (scalar)0;
-                    Z[sb][rb][v] = diag ? 1.f : 0.f;
+                    const scalar E = L::pow2(x[(sb * NB + tb) * 4 + v] - m);
+#pragma unroll
+                    for (int rb = 0; rb < NB; ++rb) acc[tb][rb] = L::mfma(E, D[sb][rb][v], acc[tb][rb]);
                 }
+        // bit e of nz: entry e of this matrix is not a structural zero
+        const auto nonzero_mask = [&]() {
+            unsigned nz = 0;
 #pragma unroll
-        for (int rb = 0; rb < NB; ++rb) esum[rb] = 0;
-        typename Src::Slot ring[Src::PF];
-        auto load = [&](int i, int slot) { src.load(i, ring[slot]); };
-        // The single-precision product looks at every position whether it still holds, and ends at
-        // once if not; the double-precision one hardly ever fails and is judged at the end.
-        const auto step = [&](int, int slot) -> bool {
-            float x[NE];
-            const double common = src.entries(ring[slot], x);
-            float mloc = x[0];
+            for (int e = 0; e < NE; ++e) nz |= (x[e] > LCCRF_NEG_INF) ? (1u << e) : 0u;
+            return nz;
+        };
+        unsigned nz = 0;
+        bool hole;
+        if constexpr (Src::kPaddingIsFinite) {
+            hole = src.smallest_loaded(ring[slot]) == LCCRF_NEG_INF;
+        } else {
+            nz = nonzero_mask();
+            hole = (in & ~nz) != 0;
+        }
+        if (!tracking && __builtin_amdgcn_ballot_w64(hole) != 0) {
+            tracking = true;
+            if (started) {
 #pragma unroll
-            for (int e = 1; e < NE; ++e) mloc = fmaxf(mloc, x[e]);
-            const float m = finite_or_zero(xor_max<1, 64>(mloc));
-            Msum += (double)m + common;
-            vec acc[NB][NB];
+                for (int sb = 0; sb < NB; ++sb)
+#pragma unroll
+                    for (int rb = 0; rb < NB; ++rb)
+#pragma unroll
+                        for (int v = 0; v < 4; ++v) Z[sb][rb][v] = (in >> ((sb * NB + rb) * 4 + v)) & 1 ? 1.f : 0.f;
+            }
+        }
+        started = true;
+        // Exponent fields of the new entries: their largest gives each column's rescale, the
+        // smallest among the entries that some path reaches says whether the product still holds.
+        unsigned fld[NB][NB][4], fmin = L::kNoField;
+#pragma unroll
+        for (int tb = 0; tb < NB; ++tb)
+#pragma unroll
+            for (int rb = 0; rb < NB; ++rb)
+#pragma unroll
+                for (int v = 0; v < 4; ++v) fld[tb][rb][v] = L::field(acc[tb][rb][v]);
+        if (tracking) {
+            if constexpr (Src::kPaddingIsFinite) nz = nonzero_mask();
+            const unsigned nzp = (unsigned)__shfl((int)nz, pj, 64);
+            f32x4 pat[NB][NB];
 #pragma unroll
             for (int tb = 0; tb < NB; ++tb)
 #pragma unroll
-                for (int rb = 0; rb < NB; ++rb) acc[tb][rb] = vec{0, 0, 0, 0};
+                for (int rb = 0; rb < NB; ++rb) pat[tb][rb] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
             for (int sb = 0; sb < NB; ++sb)
 #pragma unroll
                 for (int tb = 0; tb < NB; ++tb)
 #pragma unroll
                     for (int v = 0; v < 4; ++v) {
-                        const scalar E = L::pow2(x[(sb * NB + tb) * 4 + v] - m);
-#pragma unroll
-                        for (int rb = 0; rb < NB; ++rb) acc[tb][rb] = L::mfma(E, D[sb][rb][v], acc[tb][rb]);
-                    }
-            // bit e of nz: entry e of this matrix is not a structural zero
-            const auto nonzero_mask = [&]() {
-                unsigned nz = 0;
-#pragma unroll
-                for (int e = 0; e < NE; ++e) nz |= (x[e] > LCCRF_NEG_INF) ? (1u << e) : 0u;
-                return nz;
-            };
-            unsigned nz = 0;
-            bool hole;
-            if constexpr (Src::kPaddingIsFinite) {
-                hole = src.smallest_loaded(ring[slot]) == LCCRF_NEG_INF;
-            } else {
-                nz = nonzero_mask();
-                hole = (in & ~nz) != 0;
-            }
-            if (!tracking && __builtin_amdgcn_ballot_w64(hole) != 0) {
-                tracking = true;
-                if (started) {
-#pragma unroll
-                    for (int sb = 0; sb < NB; ++sb)
+                        const float flag = (nzp >> ((sb * NB + tb) * 4 + v)) & 1 ? 1.f : 0.f;
 #pragma unroll
                         for (int rb = 0; rb < NB; ++rb)
-#pragma unroll
-                            for (int v = 0; v < 4; ++v) Z[sb][rb][v] = (in >> ((sb * NB + rb) * 4 + v)) & 1 ? 1.f : 0.f;
-                }
-            }
-            started = true;
-            // Exponent fields of the new entries: their largest gives each column's rescale, the
-            // smallest among the entries that some path reaches says whether the product still holds.
-            unsigned fld[NB][NB][4], fmin = L::kNoField;
-#pragma unroll
-            for (int tb = 0; tb < NB; ++tb)
-#pragma unroll
-                for (int rb = 0; rb < NB; ++rb)
-#pragma unroll
-                    for (int v = 0; v < 4; ++v) fld[tb][rb][v] = L::field(acc[tb][rb][v]);
-            if (tracking) {
-                if constexpr (Src::kPaddingIsFinite) nz = nonzero_mask();
-                const unsigned nzp = (unsigned)__shfl((int)nz, pj, 64);
-                f32x4 pat[NB][NB];
-#pragma unroll
-                for (int tb = 0; tb < NB; ++tb)
-#pragma unroll
-                    for (int rb = 0; rb < NB; ++rb) pat[tb][rb] = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-                for (int sb = 0; sb < NB; ++sb)
-#pragma unroll
-                    for (int tb = 0; tb < NB; ++tb)
-#pragma unroll
-                        for (int v = 0; v < 4; ++v) {
-                            const float flag = (nzp >> ((sb * NB + tb) * 4 + v)) & 1 ? 1.f : 0.f;
-#pragma unroll
-                            for (int rb = 0; rb < NB; ++rb)
-                                pat[tb][rb] = __builtin_amdgcn_mfma_f32_16x16x4f32(flag, Z[sb][rb][v], pat[tb][rb], 0, 0, 0);
-                        }
-#pragma unroll
-                for (int tb = 0; tb < NB; ++tb)
-#pragma unroll
-                    for (int rb = 0; rb < NB; ++rb)
-#pragma unroll
-                        for (int v = 0; v < 4; ++v) {
-                            const bool reached = pat[tb][rb][v] > 0.f;
-                            Z[tb][rb][v] = reached ? 1.f : 0.f;
-                            fmin = min(fmin, reached ? fld[tb][rb][v] : L::kNoField);
-                        }
-            } else {
-#pragma unroll
-                for (int tb = 0; tb < NB; ++tb)
-#pragma unroll
-                    for (int rb = 0; rb < NB; ++rb)
-#pragma unroll
-                        for (int v = 0; v < 4; ++v)
-                            fmin = min(fmin, (in >> ((tb * NB + rb) * 4 + v)) & 1 ? fld[tb][rb][v] : L::kNoField);
-            }
-            bad |= fmin < L::kMinField;  // also zero and subnormal entries (field 0)
-            if (!F64 && __builtin_amdgcn_ballot_w64(bad) != 0) {
-                rejected = true;
-                return false;
-            }
-            // With the column maxima of D in [1, 2) and E at most 1, a term lost to underflow is
-            // below the smallest normal number: it cannot matter to a sum of the accepted size.
-            // Power-of-two rescale of each entry tag's column (exact): the largest exponent.
-#pragma unroll
-            for (int rb = 0; rb < NB; ++rb) {
-                unsigned ef = 0;
-#pragma unroll
-                for (int tb = 0; tb < NB; ++tb)
-#pragma unroll
-                    for (int v = 0; v < 4; ++v) ef = max(ef, fld[tb][rb][v]);
-                const auto r16 = __builtin_amdgcn_permlane16_swap(ef, ef, false, false);
-                ef = max(r16[0], r16[1]);
-                const auto r32 = __builtin_amdgcn_permlane32_swap(ef, ef, false, false);
-                ef = max(r32[0], r32[1]);
-                const int ex = ef > 0 ? (int)ef - (int)L::kBias : 0;  // a column without any path keeps its zeros
-                esum[rb] += ex;
-#pragma unroll
-                for (int tb = 0; tb < NB; ++tb)
-#pragma unroll
-                    for (int v = 0; v < 4; ++v) D[tb][rb][v] = L::scaled(acc[tb][rb][v], ex);
-            }
-            return true;
-        };
-        if constexpr (F64) walk<Src::PF>(first, last, +1, load, step);
-        else walk_while<Src::PF>(first, last, +1, load, step);
-        rejected |= __builtin_amdgcn_ballot_w64(bad) != 0;
-        if (!rejected) {
-            float ef[NB], emax = LCCRF_NEG_INF;
-#pragma unroll
-            for (int rb = 0; rb < NB; ++rb) {
-                ef[rb] = 16 * rb + j < T ? (float)esum[rb] : LCCRF_NEG_INF;
-                emax = fmaxf(emax, xor_max<1, 16>(ef[rb]));
-            }
-            emax = finite_or_zero(emax);
+                            pat[tb][rb] = __builtin_amdgcn_mfma_f32_16x16x4f32(flag, Z[sb][rb][v], pat[tb][rb], 0, 0, 0);
+                    }
 #pragma unroll
             for (int tb = 0; tb < NB; ++tb)
 #pragma unroll
                 for (int rb = 0; rb < NB; ++rb)
 #pragma unroll
                     for (int v = 0; v < 4; ++v) {
-                        const bool inside = (in >> ((tb * NB + rb) * 4 + v)) & 1;
-                        Pout[S::row(lane, (tb * NB + rb) * 4 + v) * TP + 16 * rb + j] =
-                            (inside && D[tb][rb][v] > 0) ? L::log2_of(D[tb][rb][v]) : LCCRF_NEG_INF;
+                        const bool reached = pat[tb][rb][v] > 0.f;
+                        Z[tb][rb][v] = reached ? 1.f : 0.f;
+                        fmin = min(fmin, reached ? fld[tb][rb][v] : L::kNoField);
                     }
-            if (g == 0) {
+        } else {
 #pragma unroll
-                for (int rb = 0; rb < NB; ++rb) rel_out[16 * rb + j] = ef[rb] - emax;
-            }
-            if (lane == 0) *base_out = Msum + (double)emax;
-            return true;
+            for (int tb = 0; tb < NB; ++tb)
+#pragma unroll
+                for (int rb = 0; rb < NB; ++rb)
+#pragma unroll
+                    for (int v = 0; v < 4; ++v)
+                        fmin = min(fmin, (in >> ((tb * NB + rb) * 4 + v)) & 1 ? fld[tb][rb][v] : L::kNoField);
         }
+        bad |= fmin < L::kMinField;  // also zero and subnormal entries (field 0)
+        if (!F64 && __builtin_amdgcn_ballot_w64(bad) != 0) {
+            rejected = true;
+            return false;
+        }
+        // With the column maxima of D in [1, 2) and E at most 1, a term lost to underflow is
+        // below the smallest normal number: it cannot matter to a sum of the accepted size.
+        // Power-of-two rescale of each entry tag's column (exact): the largest exponent.
+#pragma unroll
+        for (int rb = 0; rb < NB; ++rb) {
+            unsigned ef = 0;
+#pragma unroll
+            for (int tb = 0; tb < NB; ++tb)
+#pragma unroll
+                for (int v = 0; v < 4; ++v) ef = max(ef, fld[tb][rb][v]);
+            const auto r16 = __builtin_amdgcn_permlane16_swap(ef, ef, false, false);
+            ef = max(r16[0], r16[1]);
+            const auto r32 = __builtin_amdgcn_permlane32_swap(ef, ef, false, false);
+            ef = max(r32[0], r32[1]);
+            const int ex = ef > 0 ? (int)ef - (int)L::kBias : 0;  // a column without any path keeps its zeros
+            esum[rb] += ex;
+#pragma unroll
+            for (int tb = 0; tb < NB; ++tb)
+#pragma unroll
+                for (int v = 0; v < 4; ++v) D[tb][rb][v] = L::scaled(acc[tb][rb][v], ex);
+        }
+        return true;
+    };
+    if constexpr (F64) walk<Src::PF>(first, last, +1, load, step);
+    else walk_while<Src::PF>(first, last, +1, load, step);
+    rejected |= __builtin_amdgcn_ballot_w64(bad) != 0;
+    if (!rejected) {
+        float ef[NB], emax = LCCRF_NEG_INF;
+#pragma unroll
+        for (int rb = 0; rb < NB; ++rb) {
+            ef[rb] = 16 * rb + j < T ? (float)esum[rb] : LCCRF_NEG_INF;
+            emax = fmaxf(emax, xor_max<1, 16>(ef[rb]));
+        }
+        emax = finite_or_zero(emax);
+#pragma unroll
+        for (int tb = 0; tb < NB; ++tb)
+#pragma unroll
+            for (int rb = 0; rb < NB; ++rb)
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    const bool inside = (in >> ((tb * NB + rb) * 4 + v)) & 1;
+                    Pout[S::row(lane, (tb * NB + rb) * 4 + v) * TP + 16 * rb + j] =
+                        (inside && D[tb][rb][v] > 0) ? L::log2_of(D[tb][rb][v]) : LCCRF_NEG_INF;
+                }
+        if (g == 0) {
+#pragma unroll
+            for (int rb = 0; rb < NB; ++rb) rel_out[16 * rb + j] = ef[rb] - emax;
+        }
+        if (lane == 0) *base_out = Msum + (double)emax;
+        return true;
     }
     return false;
 }
@@ -438,63 +436,61 @@ __device__ __forceinline__ void exact_product(const Src& src, int first, int las
                                               float (*Pc)[TP + 1], float (*Ph)[TP + 1]) {
     using S = ScanShape<TP, true>;
     const int lane = threadIdx.x;
-    {
-        constexpr int LPRow = S::LPRow, CPL = S::CPL;
-        const int r = lane / LPRow, q = lane % LPRow;
-        float out[CPL];
+    constexpr int LPRow = S::LPRow, CPL = S::CPL;
+    const int r = lane / LPRow, q = lane % LPRow;
+    float out[CPL];
 #pragma unroll
-        for (int jj = 0; jj < CPL; ++jj) out[jj] = (r == CPL * q + jj) ? 0.f : LCCRF_NEG_INF;
-        float sg = 0.f;  // integer valued
-        double osum = 0.0;
-        for (int i = first; i <= last; ++i) {
-            osum += src.offset(i);
-            __syncthreads();
-#pragma unroll
-            for (int jj = 0; jj < CPL; ++jj) {
-                const int t = CPL * q + jj;
-                Pc[r][t] = out[jj];
-                Ph[r][t] = src.entry(i, r, t);
-            }
-            __syncthreads();
-            float mx[CPL], sm[CPL];
-#pragma unroll
-            for (int jj = 0; jj < CPL; ++jj) {
-                mx[jj] = LCCRF_NEG_INF;
-                sm[jj] = 0.f;
-            }
-            for (int s = 0; s < TP; ++s) {
-                const float p = Pc[r][s];
-#pragma unroll
-                for (int jj = 0; jj < CPL; ++jj) mx[jj] = fmaxf(mx[jj], p + Ph[s][CPL * q + jj]);
-            }
-            for (int s = 0; s < TP; ++s) {
-                const float p = Pc[r][s];
-#pragma unroll
-                for (int jj = 0; jj < CPL; ++jj) sm[jj] += ex2(p + Ph[s][CPL * q + jj] - finite_or_zero(mx[jj]));
-            }
-            float rm = LCCRF_NEG_INF;
-#pragma unroll
-            for (int jj = 0; jj < CPL; ++jj) {
-                out[jj] = mx[jj] + lg2(sm[jj]);
-                rm = fmaxf(rm, out[jj]);
-            }
-            // shift the row by the integer part of its maximum: scales stay integers, hence exact
-            rm = xor_max<1, LPRow>(rm);
-            const float sh = floorf(finite_or_zero(rm));
-            sg += sh;
-#pragma unroll
-            for (int jj = 0; jj < CPL; ++jj) out[jj] -= sh;
-        }
-        const float ef = r < T ? sg : LCCRF_NEG_INF;
-        const float emax = finite_or_zero(xor_max<LPRow, 64>(ef));
+    for (int jj = 0; jj < CPL; ++jj) out[jj] = (r == CPL * q + jj) ? 0.f : LCCRF_NEG_INF;
+    float sg = 0.f;  // integer valued
+    double osum = 0.0;
+    for (int i = first; i <= last; ++i) {
+        osum += src.offset(i);
+        __syncthreads();
 #pragma unroll
         for (int jj = 0; jj < CPL; ++jj) {
             const int t = CPL * q + jj;
-            Pout[t * TP + r] = (r < T && t < T) ? out[jj] : LCCRF_NEG_INF;
+            Pc[r][t] = out[jj];
+            Ph[r][t] = src.entry(i, r, t);
         }
-        if (q == 0) rel_out[r] = ef - emax;
-        if (lane == 0) *base_out = osum + (double)emax;
+        __syncthreads();
+        float mx[CPL], sm[CPL];
+#pragma unroll
+        for (int jj = 0; jj < CPL; ++jj) {
+            mx[jj] = LCCRF_NEG_INF;
+            sm[jj] = 0.f;
+        }
+        for (int s = 0; s < TP; ++s) {
+            const float p = Pc[r][s];
+#pragma unroll
+            for (int jj = 0; jj < CPL; ++jj) mx[jj] = fmaxf(mx[jj], p + Ph[s][CPL * q + jj]);
+        }
+        for (int s = 0; s < TP; ++s) {
+            const float p = Pc[r][s];
+#pragma unroll
+            for (int jj = 0; jj < CPL; ++jj) sm[jj] += ex2(p + Ph[s][CPL * q + jj] - finite_or_zero(mx[jj]));
+        }
+        float rm = LCCRF_NEG_INF;
+#pragma unroll
+        for (int jj = 0; jj < CPL; ++jj) {
+            out[jj] = mx[jj] + lg2(sm[jj]);
+            rm = fmaxf(rm, out[jj]);
+        }
+        // shift the row by the integer part of its maximum: scales stay integers, hence exact
+        rm = xor_max<1, LPRow>(rm);
+        const float sh = floorf(finite_or_zero(rm));
+        sg += sh;
+#pragma unroll
+        for (int jj = 0; jj < CPL; ++jj) out[jj] -= sh;
     }
+    const float ef = r < T ? sg : LCCRF_NEG_INF;
+    const float emax = finite_or_zero(xor_max<LPRow, 64>(ef));
+#pragma unroll
+    for (int jj = 0; jj < CPL; ++jj) {
+        const int t = CPL * q + jj;
+        Pout[t * TP + r] = (r < T && t < T) ? out[jj] : LCCRF_NEG_INF;
+    }
+    if (q == 0) rel_out[r] = ef - emax;
+    if (lane == 0) *base_out = osum + (double)emax;
 }
 
 // One wave per chunk: the product of the chunk's potentials.
