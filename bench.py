@@ -179,14 +179,19 @@ def main():
         f"(pass 1 {sum(pass1) / len(pass1):.4f}, pass 2 {pass2_avg:.4f}), median call {median(whole):.4f} ms")
 
     value = pots / (ms_per_step * 1e-3)
-    # dominant kernel: second pass = one read of phi + one write of mu over the positions in the chains
-    alg_bytes = eff_pots * (esz + 4)
-    achieved = alg_bytes / (pass2_avg * 1e-3) / 1e9
     call_bytes = eff_pots * (2 * esz + 4)
-    # With few sequences and T = 128 that pass is the two-workgroups-per-chain kernel (plus two
-    # few-microsecond helpers the event interval also covers: mailbox reset, exact fix-up launch).
-    paired = w.T == 128 and 4 * w.B <= torch.cuda.get_device_properties(dev).multi_processor_count
-    kernel = "pair_marginal_kernel" if paired else ("wave_marginal_kernel" if w.T <= 32 else "chain_marginal_kernel")
+    if crf.auto_algo(crf.OP_MARGINALS, w.B, w.N, w.T) == crf.ALGO_SCAN:
+        # Chunked scan: the interval after the boundary phases is one kernel that makes both passes over
+        # every chunk (two reads of phi, the second from cache at best, and one write of mu).
+        kernel, alg_bytes = "wave_chunk_kernel", call_bytes
+    else:
+        # dominant kernel: second pass = one read of phi + one write of mu over the positions in the chains.
+        # With few sequences and T = 128 that pass is the two-workgroups-per-chain kernel (plus two
+        # few-microsecond helpers the event interval also covers: mailbox reset, exact fix-up launch).
+        alg_bytes = eff_pots * (esz + 4)
+        paired = w.T == 128 and 4 * w.B <= torch.cuda.get_device_properties(dev).multi_processor_count
+        kernel = "pair_marginal_kernel" if paired else ("wave_marginal_kernel" if w.T <= 32 else "chain_marginal_kernel")
+    achieved = alg_bytes / (pass2_avg * 1e-3) / 1e9
     roofline = {"bound": "hbm", "kernel": kernel,
                 "achieved": achieved, "peak": HBM_PEAK_GBPS,
                 "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS, "traffic": stored_traffic(w.key),

@@ -260,6 +260,12 @@ int lccrf_argmax_structured(const float* emit, const float* trans, const int32_t
  * inside a query.  Results do not depend on it beyond rounding. */
 int lccrf_set_scan_chunk(int chunk);
 
+/* The schedule LCCRF_ALGO_AUTO takes for `op` at this shape under the current chunk size:
+ * LCCRF_ALGO_SEQUENTIAL or LCCRF_ALGO_SCAN.  Host-side arithmetic, nothing is launched;
+ * LCCRF_EINVAL for a shape or op the library does not serve.  For callers that size or time a run
+ * by the schedule it will take (the benchmark names its dominant kernel from it). */
+int lccrf_auto_algo(lccrf_op op, int B, int N, int T);
+
 /* Static, human-readable text for a status code. */
 const char* lccrf_strerror(int code);
 

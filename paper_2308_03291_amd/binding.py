@@ -32,8 +32,8 @@ EXPORTS = (
     "lccrf_log_partition_algo", "lccrf_marginals_algo", "lccrf_argmax_algo",
     "lccrf_marginals_timed", "lccrf_log_prob", "lccrf_entropy", "lccrf_cross_entropy", "lccrf_kl_divergence",
     "lccrf_sample", "lccrf_semi_markov_log_partition", "lccrf_log_partition_structured",
-    "lccrf_marginals_structured", "lccrf_argmax_structured", "lccrf_set_scan_chunk", "lccrf_strerror",
-    "lccrf_version",
+    "lccrf_marginals_structured", "lccrf_argmax_structured", "lccrf_set_scan_chunk", "lccrf_auto_algo",
+    "lccrf_strerror", "lccrf_version",
 )
 
 _lib = None
@@ -89,6 +89,8 @@ def load_library() -> ctypes.CDLL:
         getattr(lib, n).restype = i
     lib.lccrf_set_scan_chunk.argtypes = [i]
     lib.lccrf_set_scan_chunk.restype = i
+    lib.lccrf_auto_algo.argtypes = [i, i, i, i]
+    lib.lccrf_auto_algo.restype = i
     _lib = lib
     return lib
 
@@ -100,6 +102,14 @@ def strerror(code: int) -> str:
 def set_scan_chunk(chunk: int) -> None:
     """Positions per chunk of ALGO_SCAN (0: default).  Size workspaces after calling this."""
     _check(load_library().lccrf_set_scan_chunk(int(chunk)), "lccrf_set_scan_chunk")
+
+
+def auto_algo(op: int, B: int, N: int, T: int) -> int:
+    """The schedule ALGO_AUTO takes for `op` at this shape: ALGO_SEQUENTIAL or ALGO_SCAN."""
+    rc = load_library().lccrf_auto_algo(int(op), int(B), int(N), int(T))
+    if rc < 0:
+        _check(rc, "lccrf_auto_algo")
+    return rc
 
 
 def _check(rc: int, what: str):

@@ -122,6 +122,11 @@ inline bool scan_pays_sum(int B, int N, int T) {
     if (scan_pays(B, N, T)) return true;
     return lccrf::scan_supported(T) && N >= 8 * g_scan_chunk && (long long)B * N <= 32768;
 }
+// The entropy-like queries make two passes under the scan against one sequential pass: with 17 .. 32
+// tags it takes chains twice as long to pay.
+inline bool scan_pays_entropy(int B, int N, int T) {
+    return scan_pays(B, N, T) || (scan_pays_sum(B, N, T) && N >= 16 * g_scan_chunk);
+}
 
 int sum_query(int op, const void* phi, int dt, const int32_t* lengths, int B, int N, int T, float* logZ,
               float* marginals, void* workspace, size_t workspace_bytes, void* stream, int algo,
@@ -186,6 +191,22 @@ size_t lccrf_workspace_bytes(lccrf_op op, int B, int N, int T, lccrf_dtype dt) {
         case LCCRF_OP_ARGMAX: return max_workspace(B, N, T).total;
         default: return 0;
     }
+}
+
+int lccrf_auto_algo(lccrf_op op, int B, int N, int T) {
+    if (!shape_ok(B, N, T)) return LCCRF_EINVAL;
+    bool scan;
+    switch (op) {
+        case LCCRF_OP_LOGZ:
+        case LCCRF_OP_MARGINALS:
+        case LCCRF_OP_LOG_PROB:
+        case LCCRF_OP_SAMPLE: scan = scan_pays_sum(B, N, T); break;
+        case LCCRF_OP_ARGMAX: scan = scan_pays(B, N, T); break;
+        case LCCRF_OP_ENTROPY:
+        case LCCRF_OP_CROSS_ENTROPY: scan = scan_pays_entropy(B, N, T); break;
+        default: return LCCRF_EINVAL;
+    }
+    return scan ? LCCRF_ALGO_SCAN : LCCRF_ALGO_SEQUENTIAL;
 }
 
 int lccrf_log_partition_algo(const void* phi, lccrf_dtype dt, const int32_t* lengths, int B, int N, int T,
@@ -296,8 +317,7 @@ int lccrf_entropy(const void* phi, lccrf_dtype dt, const int32_t* lengths, int B
     if (!aligned_to(entropy, 4) || (lengths && !aligned_to(lengths, 4))) return LCCRF_EALIGN;
     const SumWorkspace w = sum_workspace(B, N, T);
     char* base = static_cast<char*>(workspace);
-    // (two passes under the scan against one sequential pass: with 17 .. 32 tags it takes chains twice as long to pay)
-    if (scan_pays(B, N, T) || (scan_pays_sum(B, N, T) && N >= 16 * g_scan_chunk)) {
+    if (scan_pays_entropy(B, N, T)) {
         // Under the chunked scan a chain cannot carry its conditional entropy across chunks; the second pass
         // adds up the entropy edge by edge instead, H = H(y_0) + sum_i H(y_i | y_{i-1}), from the marginals
         // it forms in registers.
@@ -342,7 +362,7 @@ static int cross_query(bool kl, const void* phi_p, const void* phi_q, lccrf_dtyp
     hipStream_t st = static_cast<hipStream_t>(stream);
     // log Z_q first: the chains of p then reuse the vectors' storage, the double-precision result stays
     hipError_t e = launch_log_partition64(phi_q, dt, lengths, B, N, T, w, base, st);
-    if (scan_pays(B, N, T) || (scan_pays_sum(B, N, T) && N >= 16 * g_scan_chunk)) {
+    if (scan_pays_entropy(B, N, T)) {
         // Long chains over few tags: the chains of p under the chunked scan, as for the entropy; the second
         // pass adds up the expectation of phi_q (of phi_q - phi_p) edge by edge from the marginals of p it
         // forms in registers.

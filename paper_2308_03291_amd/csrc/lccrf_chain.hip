@@ -977,6 +977,13 @@ hipError_t launch_chunked_marginals(int dtype, const void* phi, const int32_t* l
     a.ent_kind = !ent ? 0 : !psi ? 1 : difference ? 3 : 2;
     if (ent) a.psi = psi;  // (only the second pass of the one-wave kernels looks at it)
     if (ent && !wave_supported(T)) return hipErrorInvalidValue;
+    if (wave_supported(T) && wave_chunks_fused(chunk)) {
+        if (between) {  // (the boundary phases lie before it, both passes of the chunks after it)
+            const hipError_t e = hipEventRecord(between, st);
+            if (e != hipSuccess) return e;
+        }
+        return launch_wave_chunks(dtype, a, st);
+    }
     if (wave_supported(T)) return launch_wave(1, dtype, a, st, between);
     const PairPlan pair{nullptr, nullptr, dtype};
     const bool aligned = (T % 4) == 0;

@@ -97,5 +97,9 @@ __device__ __forceinline__ int forward_end(const ChainArgs& a, int p0, int e) { 
 // second writes the marginals.  dtype 0: float, 1: bfloat16.
 bool wave_supported(int T);
 hipError_t launch_wave_pass(bool second_pass, int dtype, const ChainArgs& a, hipStream_t st);
+// Chunked schedule with chunks short enough (wave_chunks_fused): both passes of every chunk in one
+// launch, one workgroup of two waves per chunk, the chunk's vectors in LDS (ua, ub, Oa, Ob unused).
+bool wave_chunks_fused(int chunk);
+hipError_t launch_wave_chunks(int dtype, const ChainArgs& a, hipStream_t st);
 
 }  // namespace lccrf

@@ -313,19 +313,33 @@ constexpr int wave_ring_depth(int TP, bool second_pass) { return second_pass ? (
 // Pass 1: both half chains, vectors stored.
 // STRUCT: potentials are trans + emit (a compile-time choice: a branch around the loads would cost the
 // exact wait counts that keep the ring of tiles in flight).
+// Where the two passes keep the vectors of a chain: position `pos` of the sequence at index
+// pos - origin (device memory: the sequence's rows of the workspace arrays, origin 0; LDS: the
+// positions of one chunk, origin = its first position).
+struct VecStore {
+    float* ua;
+    float* ub;
+    double* Oa;
+    double* Ob;
+    int origin;
+};
+
+__device__ __forceinline__ VecStore device_vectors(const ChainArgs& a, int b) {
+    const size_t vb = (size_t)b * a.N;
+    return VecStore{a.ua + vb * a.T, a.ub + vb * a.T, a.Oa + vb, a.Ob + vb, 0};
+}
+
 template <int TP, typename TIN, bool ALIGNED, bool WITH_H, bool STRUCT>
-__global__ __launch_bounds__(64) void wave_half_kernel(ChainArgs a) {
+__device__ __forceinline__ void wave_half_body(const ChainArgs& a, const Span& sp, int dir, int lane, const VecStore& vs) {
     using W = WGeo<TP>;
     constexpr int R = W::R, PF = wave_ring_depth(TP, false);
-    const int lane = threadIdx.x, cg = lane % W::CG, rg = lane / W::CG, c4 = 4 * cg, s0 = R * rg;
-    const int dir = blockIdx.x & 1;
-    const Span sp = make_span(a, blockIdx.x >> 1);
+    const int cg = lane % W::CG, rg = lane / W::CG, c4 = 4 * cg, s0 = R * rg;
     if (sp.empty) return;
     const int b = sp.b, N = a.N, T = a.T;
     const int p0 = sp.p0, e = sp.e;
     const int h = forward_end(a, p0, e);
     if (a.full_forward && dir == 1) return;
-    const size_t TT = (size_t)T * T, vb = (size_t)b * N;
+    const size_t TT = (size_t)T * T;
     const TIN* phib = static_cast<const TIN*>(a.phi) + (size_t)b * N * TT;
     const bool exact_only = a.exact_only != 0;
     float ring[PF][R][4];
@@ -364,9 +378,9 @@ __global__ __launch_bounds__(64) void wave_half_kernel(ChainArgs a) {
             if (rg == 0) {
 #pragma unroll
                 for (int j = 0; j < 4; ++j)
-                    if (c4 + j < T) a.ua[(vb + pos) * T + c4 + j] = vc[j];
+                    if (c4 + j < T) vs.ua[(pos - vs.origin) * T + c4 + j] = vc[j];
             }
-            if (lane == 0) a.Oa[vb + pos] = O;
+            if (lane == 0) vs.Oa[pos - vs.origin] = O;
             return d;
         };
         float hc[4] = {0.f, 0.f, 0.f, 0.f};  // entropy of the path behind each tag, column form
@@ -405,9 +419,9 @@ __global__ __launch_bounds__(64) void wave_half_kernel(ChainArgs a) {
             if (cg == 0) {
 #pragma unroll
                 for (int k = 0; k < R; ++k)
-                    if (s0 + k < T) a.ub[(vb + pos) * T + s0 + k] = vr[k];
+                    if (s0 + k < T) vs.ub[(pos - vs.origin) * T + s0 + k] = vr[k];
             }
-            if (lane == 0) a.Ob[vb + pos] = O;
+            if (lane == 0) vs.Ob[pos - vs.origin] = O;
             return d;
         };
         float hr[R];  // entropy of the path ahead of each tag, row form
@@ -430,6 +444,12 @@ __global__ __launch_bounds__(64) void wave_half_kernel(ChainArgs a) {
     }
 }
 
+template <int TP, typename TIN, bool ALIGNED, bool WITH_H, bool STRUCT>
+__global__ __launch_bounds__(64) void wave_half_kernel(ChainArgs a) {
+    const Span sp = make_span(a, blockIdx.x >> 1);
+    wave_half_body<TP, TIN, ALIGNED, WITH_H, STRUCT>(a, sp, blockIdx.x & 1, threadIdx.x, device_vectors(a, sp.b));
+}
+
 // ---------------------------------------------------------------------------------------
 // Pass 2: both chains continue past the meeting point and write the marginals.
 // ENT: no marginal is written; every wave adds up the conditional entropies H(y_i | y_{i-1}) of its
@@ -438,14 +458,13 @@ __global__ __launch_bounds__(64) void wave_half_kernel(ChainArgs a) {
 // ENT = 2: the same with the expectation of a second chain's potentials a.psi under this chain's
 // marginals, sum_e mu(e) psi(e) (a.ent_kind = 2), or of psi - phi (a.ent_kind = 3), in natural units.
 template <int TP, typename TIN, bool ALIGNED, bool STRUCT, int ENT = 0>
-__global__ __launch_bounds__(64) void wave_marginal_kernel(ChainArgs a) {
+__device__ __forceinline__ void wave_marginal_body(const ChainArgs& a, const Span& sp, int dir, int lane, const VecStore& vs) {
     using W = WGeo<TP>;
     constexpr int R = W::R, PF = wave_ring_depth(TP, true);
-    const int lane = threadIdx.x, cg = lane % W::CG, rg = lane / W::CG, c4 = 4 * cg, s0 = R * rg;
-    const int dir = blockIdx.x & 1;
-    const Span sp = make_span(a, blockIdx.x >> 1);
+    const int cg = lane % W::CG, rg = lane / W::CG, c4 = 4 * cg, s0 = R * rg;
     const int b = sp.b, N = a.N, T = a.T, L = sp.L;
-    const size_t TT = (size_t)T * T, vb = (size_t)b * N;
+    const size_t TT = (size_t)T * T;
+    const int og = vs.origin;
     float* mub = ENT != 0 ? nullptr : a.mu + (size_t)b * N * TT;
     const bool exact_only = a.exact_only != 0;
     float hacc = 0.f;
@@ -478,12 +497,12 @@ __global__ __launch_bounds__(64) void wave_marginal_kernel(ChainArgs a) {
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             const int t = c4 + j;
-            z[j] = (t < T) ? a.ua[(vb + h) * T + t] + a.ub[(vb + h) * T + t] : LCCRF_NEG_INF;
+            z[j] = (t < T) ? vs.ua[(h - og) * T + t] + vs.ub[(h - og) * T + t] : LCCRF_NEG_INF;
         }
         const float M = xor_max<1, W::CG>(max4(z));
         const float g = finite_or_zero(M);
         const float S = xor_sum<1, W::CG>((ex2(z[0] - g) + ex2(z[1] - g)) + (ex2(z[2] - g) + ex2(z[3] - g)));
-        lz2 = (double)(M + lg2(S)) + a.Oa[vb + h] + a.Ob[vb + h];
+        lz2 = (double)(M + lg2(S)) + vs.Oa[h - og] + vs.Ob[h - og];
     }
     const bool feasible = lz2 > -1.0e300;  // false: no path has a finite score, marginals are 0
     if (dir == 0 && sp.c == 0 && lane == 0 && a.logZ) a.logZ[b] = (float)(lz2 * kLn2);
@@ -518,17 +537,17 @@ __global__ __launch_bounds__(64) void wave_marginal_kernel(ChainArgs a) {
     for (int k = 0; k < R; ++k) noh_r[k] = 0.f;
 
     if (dir == 0) {
-        double O = a.Oa[vb + h];
+        double O = vs.Oa[h - og];
         float vc[4];
 #pragma unroll
-        for (int j = 0; j < 4; ++j) vc[j] = (c4 + j < T) ? a.ua[(vb + h) * T + c4 + j] : LCCRF_NEG_INF;
+        for (int j = 0; j < 4; ++j) vc[j] = (c4 + j < T) ? vs.ua[(h - og) * T + c4 + j] : LCCRF_NEG_INF;
         float aux[PF][4];
         double ob[PF];
         auto load = [&](int i, int slot) {
             load_phi(i, slot);
 #pragma unroll
-            for (int j = 0; j < 4; ++j) aux[slot][j] = a.ub[(vb + i) * T + (c4 + j < T ? c4 + j : T - 1)];
-            ob[slot] = a.Ob[vb + i];
+            for (int j = 0; j < 4; ++j) aux[slot][j] = vs.ub[(i - og) * T + (c4 + j < T ? c4 + j : T - 1)];
+            ob[slot] = vs.Ob[i - og];
         };
         walk<PF>(h + 1, e, +1, load, [&](int i, int slot) {
             if constexpr (structured) add_trans<R>(ring[slot], tr);
@@ -547,17 +566,17 @@ __global__ __launch_bounds__(64) void wave_marginal_kernel(ChainArgs a) {
             wave_fwd_step<TP, true, ALIGNED, false, ENT>(ring[slot], ua, d, ubK, ENT != 0 ? nullptr : mub + (size_t)i * TT, T, lane, exact_only, vc, tot, noh_r, noh_c, hacc, wt);
         });
     } else {
-        double O = a.Ob[vb + h];
+        double O = vs.Ob[h - og];
         float vr[R];
 #pragma unroll
-        for (int k = 0; k < R; ++k) vr[k] = (s0 + k < T) ? a.ub[(vb + h) * T + s0 + k] : LCCRF_NEG_INF;
+        for (int k = 0; k < R; ++k) vr[k] = (s0 + k < T) ? vs.ub[(h - og) * T + s0 + k] : LCCRF_NEG_INF;
         float aux[PF][R];
         double oa[PF];
         auto load = [&](int i, int slot) {
             load_phi(i, slot);
 #pragma unroll
-            for (int k = 0; k < R; ++k) aux[slot][k] = a.ua[(vb + i - 1) * T + (s0 + k < T ? s0 + k : T - 1)];
-            oa[slot] = a.Oa[vb + i - 1];
+            for (int k = 0; k < R; ++k) aux[slot][k] = vs.ua[(i - 1 - og) * T + (s0 + k < T ? s0 + k : T - 1)];
+            oa[slot] = vs.Oa[i - 1 - og];
         };
         walk<PF>(h, p0 + 1, -1, load, [&](int i, int slot) {
             if constexpr (structured) add_trans<R>(ring[slot], tr);
@@ -591,7 +610,7 @@ __global__ __launch_bounds__(64) void wave_marginal_kernel(ChainArgs a) {
         float z[R], m = LCCRF_NEG_INF;
 #pragma unroll
         for (int k = 0; k < R; ++k) {
-            z[k] = (s0 + k < T) ? a.ua[vb * T + s0 + k] + vr[k] : LCCRF_NEG_INF;
+            z[k] = (s0 + k < T) ? vs.ua[(0 - og) * T + s0 + k] + vr[k] : LCCRF_NEG_INF;
             m = fmaxf(m, z[k]);
         }
         m = finite_or_zero(xor_max<W::CG, 64>(m));
@@ -622,8 +641,52 @@ __global__ __launch_bounds__(64) void wave_marginal_kernel(ChainArgs a) {
     }
 }
 
+template <int TP, typename TIN, bool ALIGNED, bool STRUCT, int ENT = 0>
+__global__ __launch_bounds__(64) void wave_marginal_kernel(ChainArgs a) {
+    const Span sp = make_span(a, blockIdx.x >> 1);
+    wave_marginal_body<TP, TIN, ALIGNED, STRUCT, ENT>(a, sp, blockIdx.x & 1, threadIdx.x, device_vectors(a, sp.b));
+}
+
+// Both passes of one chunk in one workgroup of two waves (the forward and the backward chain), the
+// vectors of the chunk's positions in LDS instead of the workspace: one launch and no trip through
+// device memory between the passes.  Chunks of at most kFusedChunk positions.
+constexpr int kFusedChunk = 64;
+
+template <int TP, typename TIN, bool ALIGNED, int ENT>
+__global__ __launch_bounds__(128) void wave_chunk_kernel(ChainArgs a) {
+    __shared__ float sua[(kFusedChunk + 1) * TP], sub[(kFusedChunk + 1) * TP];
+    __shared__ double sOa[kFusedChunk + 1], sOb[kFusedChunk + 1];
+    const int lane = threadIdx.x & 63, dir = threadIdx.x >> 6;
+    const Span sp = make_span(a, blockIdx.x);
+    const VecStore vs{sua, sub, sOa, sOb, sp.p0};
+    wave_half_body<TP, TIN, ALIGNED, false, false>(a, sp, dir, lane, vs);
+    __syncthreads();
+    wave_marginal_body<TP, TIN, ALIGNED, false, ENT>(a, sp, dir, lane, vs);
+}
+
 // ---------------------------------------------------------------------------------------
 bool wave_supported(int T) { return T >= 1 && T <= 32; }
+bool wave_chunks_fused(int chunk) { return chunk >= 1 && chunk <= kFusedChunk; }
+
+template <int TP, typename TIN, bool ALIGNED>
+static hipError_t launch_wave_chunks_tp(const ChainArgs& a, hipStream_t st) {
+    const dim3 grid(a.B * a.C), block(128);
+    if (a.ent && a.ent_kind >= 2) hipLaunchKernelGGL((wave_chunk_kernel<TP, TIN, ALIGNED, 2>), grid, block, 0, st, a);
+    else if (a.ent) hipLaunchKernelGGL((wave_chunk_kernel<TP, TIN, ALIGNED, 1>), grid, block, 0, st, a);
+    else hipLaunchKernelGGL((wave_chunk_kernel<TP, TIN, ALIGNED, 0>), grid, block, 0, st, a);
+    return hipGetLastError();
+}
+
+// Both passes over every chunk of `a` in one launch (a.chunk > 0, wave_chunks_fused(a.chunk), plain potentials).
+hipError_t launch_wave_chunks(int dtype, const ChainArgs& a, hipStream_t st) {
+    const bool aligned = (a.T % 4) == 0;
+    if (a.T <= 16) {
+        if (dtype == 0) return aligned ? launch_wave_chunks_tp<16, float, true>(a, st) : launch_wave_chunks_tp<16, float, false>(a, st);
+        return aligned ? launch_wave_chunks_tp<16, uint16_t, true>(a, st) : launch_wave_chunks_tp<16, uint16_t, false>(a, st);
+    }
+    if (dtype == 0) return aligned ? launch_wave_chunks_tp<32, float, true>(a, st) : launch_wave_chunks_tp<32, float, false>(a, st);
+    return aligned ? launch_wave_chunks_tp<32, uint16_t, true>(a, st) : launch_wave_chunks_tp<32, uint16_t, false>(a, st);
+}
 
 template <int TP, typename TIN, bool ALIGNED>
 static hipError_t launch_wave_tp(bool second_pass, const ChainArgs& a, hipStream_t st) {

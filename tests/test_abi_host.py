@@ -53,6 +53,21 @@ def test_workspace_sizes(lib):
     assert binding.workspace_bytes(9, 1, 8, 8, 0) == 0
 
 
+def test_auto_schedule_is_reported_without_a_gpu(lib):
+    """lccrf_auto_algo is host arithmetic: long chains over few tags in small batches take the scan."""
+    assert binding.auto_algo(binding.OP_MARGINALS, 4, 16384, 16) == binding.ALGO_SCAN       # config 5
+    assert binding.auto_algo(binding.OP_ARGMAX, 4, 16384, 16) == binding.ALGO_SCAN
+    assert binding.auto_algo(binding.OP_MARGINALS, 64, 512, 128) == binding.ALGO_SEQUENTIAL  # config 4
+    assert binding.auto_algo(binding.OP_MARGINALS, 128, 256, 32) == binding.ALGO_SCAN        # the paper's size
+    assert binding.auto_algo(binding.OP_ARGMAX, 128, 256, 32) == binding.ALGO_SEQUENTIAL     # max-plus scan: 16 tags
+    assert binding.auto_algo(binding.OP_ENTROPY, 128, 256, 32) == binding.ALGO_SEQUENTIAL
+    assert binding.auto_algo(binding.OP_MARGINALS, 32, 64, 32) == binding.ALGO_SEQUENTIAL    # config 2
+    with pytest.raises(binding.LccrfError):
+        binding.auto_algo(binding.OP_MARGINALS, 1, 8, 0)
+    with pytest.raises(binding.LccrfError):
+        binding.auto_algo(99, 1, 8, 4)
+
+
 def test_bad_arguments_are_rejected_without_a_gpu(lib):
     fake = 4096  # a non-null, aligned "pointer" that is never dereferenced on these paths
     ws = 1 << 20

@@ -10,6 +10,8 @@ from test_gpu_parity import check_case, crf  # noqa: F401  (fixture)
 
 pytestmark = pytest.mark.gpu
 
+SUMS = ("logz", "mu")   # the scan of the max-plus semiring stops at 16 tags
+
 
 @pytest.fixture
 def chunk(crf):
@@ -40,6 +42,18 @@ def test_scan_one_chunk_and_many_chunks(crf, oracle_mod, chunk, k):
     chunk(k)
     phi, lens = workloads.random_case(5100 + k, 6, N, 16, scale=2.0, ragged=True, min_len=1)
     check_case(crf, oracle_mod, phi, lens, algo=crf.ALGO_SCAN, what=f"scan C={N // k}")
+
+
+@pytest.mark.parametrize("T", [16, 27])
+def test_scan_chunks_longer_than_the_fused_kernel_takes(crf, oracle_mod, chunk, T):
+    """Chunks of more than 64 positions run the two passes inside the chunks as two launches with the
+    vectors in the workspace (shorter ones: one launch, vectors in LDS)."""
+    chunk(100)
+    phi, lens = workloads.random_case(5150 + T, 4, 1700, T, scale=2.0, ragged=True, min_len=90)
+    check_case(crf, oracle_mod, phi, lens, algo=crf.ALGO_SCAN, what=f"scan chunk 100 T={T}", queries=SUMS)
+    H = crf.lccrf_entropy(phi.cuda(), lens.cuda()).cpu().numpy()
+    want = oracle_mod.entropy(phi, lens.numpy())
+    assert np.all(np.abs(H - want) <= 2e-4 * np.maximum(1.0, np.abs(want)))
 
 
 def test_scan_bf16(crf, oracle_mod, chunk):
@@ -125,9 +139,6 @@ def test_scan_repeat_runs_are_bit_identical(crf):
     lz_a, mu_a = crf.lccrf_marginals(dphi, dl, algo=crf.ALGO_SCAN)
     lz_b, mu_b = crf.lccrf_marginals(dphi, dl, algo=crf.ALGO_SCAN)
     assert torch.equal(lz_a, lz_b) and torch.equal(mu_a, mu_b)
-
-
-SUMS = ("logz", "mu")   # the scan of the max-plus semiring stops at 16 tags
 
 
 @pytest.mark.parametrize("k", [4, 7, 32])
