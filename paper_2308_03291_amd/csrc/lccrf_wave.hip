@@ -307,7 +307,7 @@ __device__ __forceinline__ void wave_bwd_step(float (&v)[WGeo<TP>::R][4], const 
 __device__ __forceinline__ float drift_of(float tot) { return (tot > 0.5f && tot < 2.0f) ? -lg2(tot) : 0.f; }
 
 // Tiles in flight per wave: more in the first pass, whose slots are smaller (no stored vector rides along).
-constexpr int wave_ring_depth(int TP, bool second_pass) { return second_pass ? (TP == 16 ? 6 : 4) : (TP == 16 ? 8 : 6); }
+constexpr int wave_ring_depth(int TP, bool second_pass) { return second_pass ? (TP == 16 ? 2 : 2) : (TP == 16 ? 8 : 6); }
 
 // ---------------------------------------------------------------------------------------
 // Pass 1: both half chains, vectors stored.
@@ -329,10 +329,10 @@ __device__ __forceinline__ VecStore device_vectors(const ChainArgs& a, int b) {
     return VecStore{a.ua + vb * a.T, a.ub + vb * a.T, a.Oa + vb, a.Ob + vb, 0};
 }
 
-template <int TP, typename TIN, bool ALIGNED, bool WITH_H, bool STRUCT>
+template <int TP, typename TIN, bool ALIGNED, bool WITH_H, bool STRUCT, int PF = wave_ring_depth(TP, false)>
 __device__ __forceinline__ void wave_half_body(const ChainArgs& a, const Span& sp, int dir, int lane, const VecStore& vs) {
     using W = WGeo<TP>;
-    constexpr int R = W::R, PF = wave_ring_depth(TP, false);
+    constexpr int R = W::R;
     const int cg = lane % W::CG, rg = lane / W::CG, c4 = 4 * cg, s0 = R * rg;
     if (sp.empty) return;
     const int b = sp.b, N = a.N, T = a.T;
@@ -651,6 +651,7 @@ __global__ __launch_bounds__(64) void wave_marginal_kernel(ChainArgs a) {
 // vectors of the chunk's positions in LDS instead of the workspace: one launch and no trip through
 // device memory between the passes.  Chunks of at most kFusedChunk positions.
 constexpr int kFusedChunk = 64;
+constexpr int kFusedFirstDepth = 3;  // tiles in flight in its first half (registers are what bounds its waves a SIMD)
 
 template <int TP, typename TIN, bool ALIGNED, int ENT>
 __global__ __launch_bounds__(128) void wave_chunk_kernel(ChainArgs a) {
@@ -659,7 +660,7 @@ __global__ __launch_bounds__(128) void wave_chunk_kernel(ChainArgs a) {
     const int lane = threadIdx.x & 63, dir = threadIdx.x >> 6;
     const Span sp = make_span(a, blockIdx.x);
     const VecStore vs{sua, sub, sOa, sOb, sp.p0};
-    wave_half_body<TP, TIN, ALIGNED, false, false>(a, sp, dir, lane, vs);
+    wave_half_body<TP, TIN, ALIGNED, false, false, kFusedFirstDepth>(a, sp, dir, lane, vs);
     __syncthreads();
     wave_marginal_body<TP, TIN, ALIGNED, false, ENT>(a, sp, dir, lane, vs);
 }
