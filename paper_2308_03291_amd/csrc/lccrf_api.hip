@@ -18,7 +18,7 @@ struct SumWorkspace {
     size_t Pl2, rel2, base2, Fv2, OF2, Gv2, OG2;  // its group level (many chunks only, else empty)
     size_t lz64, ha, hb, hoff;             // log-probability, entropy and cross-entropy queries
     size_t ent, lzf;                       // entropy under the scan: per-chunk sums, logZ as float
-    size_t maps;                           // sampling: the map of every position, [B][N][T] bytes
+    size_t maps, winmaps;                  // sampling: the map of every position, [B][N][T] bytes; of every window
     size_t total;
 };
 inline SumWorkspace sum_workspace(size_t B, size_t N, size_t T) {
@@ -56,6 +56,7 @@ inline SumWorkspace sum_workspace(size_t B, size_t N, size_t T) {
     w.ent = off; off += round_up(BC * 2 * sizeof(float));
     w.lzf = off; off += round_up(B * sizeof(float));
     w.maps = off; off += round_up(B * N * T);
+    w.winmaps = off; off += round_up(lccrf::sample_winmap_bytes((int)B, (int)N, (int)T));
     w.total = off;
     return w;
 }
@@ -447,7 +448,8 @@ int lccrf_sample(const void* phi, lccrf_dtype dt, const int32_t* lengths, const 
     }
     if (e == hipSuccess)
         e = lccrf::launch_backward_sample(dt, phi, lengths, ua, Oa, uniforms, B, N, T,
-                                          reinterpret_cast<uint8_t*>(base + w.maps), tags, st);
+                                          reinterpret_cast<uint8_t*>(base + w.maps),
+                                          reinterpret_cast<uint8_t*>(base + w.winmaps), tags, st);
     return e == hipSuccess ? LCCRF_OK : LCCRF_ELAUNCH;
 }
 

@@ -570,34 +570,19 @@ __global__ __launch_bounds__(256) void sample_map_kernel(const TIN* __restrict__
 
 constexpr int kWalkWindow = 16384;  // bytes of the table of maps held in LDS at a time
 
-// One wave per sequence: draws y_{L-1} from alpha_{L-1}, then follows the maps down.  K tags a lane
-// (lane l owns tags l K .. l K + K - 1, so that lane-wise prefix sums keep the tag order).
+// The tag of the last position: inversion over exp(alpha_{L-1}) by one wave, K tags a lane (lane l owns
+// tags l K .. l K + K - 1, so that lane-wise prefix sums keep the tag order).  -1: no finite path.
 template <int K>
-__global__ __launch_bounds__(64) void sample_walk_kernel(const int32_t* __restrict__ lengths, const float* __restrict__ ua,
-                                                         const float* __restrict__ uniforms, const uint8_t* __restrict__ F,
-                                                         int N, int T, int32_t* __restrict__ tags) {
-    __shared__ __attribute__((aligned(16))) uint8_t win[kWalkWindow];
-    __shared__ uint8_t segmap[64 * 256];
-    __shared__ uint8_t entry[65];
-    const int b = blockIdx.x, lane = threadIdx.x;
-    const int L = clamp_length(lengths, b, N);
-    int32_t* y = tags + (size_t)b * N;
-    for (int i = L + lane; i < N; i += 64) y[i] = -1;
-    if (L == 0) return;
-    const size_t vb = (size_t)b * N;
-    // the last position: inversion over exp(alpha_{L-1})
+__device__ __forceinline__ int draw_last_tag(const float* __restrict__ alpha_last, float u, int T, int lane) {
     float w[K], m = LCCRF_NEG_INF;
 #pragma unroll
     for (int k = 0; k < K; ++k) {
         const int s = lane * K + k;
-        w[k] = s < T ? ua[(vb + L - 1) * T + s] : LCCRF_NEG_INF;
+        w[k] = s < T ? alpha_last[s] : LCCRF_NEG_INF;
         m = fmaxf(m, w[k]);
     }
     m = xor_max<1, 64>(m);
-    if (m == LCCRF_NEG_INF) {  // no finite path: all tags 0
-        for (int i = lane; i < L; i += 64) y[i] = 0;
-        return;
-    }
+    if (m == LCCRF_NEG_INF) return -1;
     float part = 0.f;
 #pragma unroll
     for (int k = 0; k < K; ++k) {
@@ -610,7 +595,7 @@ __global__ __launch_bounds__(64) void sample_walk_kernel(const int32_t* __restri
         const float v = __shfl_up(incl, off, 64);
         if (lane >= off) incl += v;
     }
-    const float target = uniforms[vb + L - 1] * __shfl(incl, 63, 64);
+    const float target = u * __shfl(incl, 63, 64);
     float cum = incl - part;
     int first_over = 0x7fffffff, last_pos = -1;
 #pragma unroll
@@ -625,72 +610,184 @@ __global__ __launch_bounds__(64) void sample_walk_kernel(const int32_t* __restri
         first_over = min(first_over, __shfl_xor(first_over, off, 64));
         last_pos = max(last_pos, __shfl_xor(last_pos, off, 64));
     }
-    int cur = first_over != 0x7fffffff ? first_over : last_pos;
+    return first_over != 0x7fffffff ? first_over : last_pos;
+}
+
+// The maps of positions lo .. lo + np - 1 of a sequence (Fb: its rows of the table) into LDS.
+__device__ __forceinline__ void load_window(uint8_t* win, const uint8_t* __restrict__ Fb, int lo, int np, int T, int lane) {
+    const uint8_t* src = Fb + (size_t)lo * T;
+    const int nbytes = np * T;
+    if (((reinterpret_cast<uintptr_t>(src) | (uintptr_t)nbytes) & 15) == 0) {
+        for (int k = lane; k < nbytes / 16; k += 64)
+            reinterpret_cast<uint4*>(win)[k] = reinterpret_cast<const uint4*>(src)[k];
+    } else {
+        for (int k = lane; k < nbytes; k += 64) win[k] = src[k];
+    }
+}
+
+// A long window is cut into 64 segments: lane l composes the maps of segment l for all T possible
+// tags above it (independent look-ups, so they overlap) into segmap[l][.].
+__device__ __forceinline__ void compose_segments(const uint8_t* win, uint8_t* segmap, int np, int T, int lane, int& bot, int& top) {
+    const int seg = (np + 63) / 64;
+    bot = lane * seg < np ? lane * seg : np;  // window-relative
+    top = bot + seg < np ? bot + seg : np;
+    for (int c0 = 0; c0 < T; c0 += 4) {
+        int t0 = c0, t1 = c0 + 1 < T ? c0 + 1 : c0, t2 = c0 + 2 < T ? c0 + 2 : c0, t3 = c0 + 3 < T ? c0 + 3 : c0;
+        for (int r = top - 1; r >= bot; --r) {
+            const uint8_t* row = win + r * T;
+            t0 = row[t0]; t1 = row[t1]; t2 = row[t2]; t3 = row[t3];
+        }
+        segmap[lane * T + c0] = (uint8_t)t0;
+        if (c0 + 1 < T) segmap[lane * T + c0 + 1] = (uint8_t)t1;
+        if (c0 + 2 < T) segmap[lane * T + c0 + 2] = (uint8_t)t2;
+        if (c0 + 3 < T) segmap[lane * T + c0 + 3] = (uint8_t)t3;
+    }
+}
+
+// Positions lo .. lo + np - 1 (their maps in win) from the tag `cur` above them, tags written to y;
+// returns the tag of position lo.  A short window is walked by one lane; a long one (small tag sets)
+// segment by segment: every lane composes its segment, one lane passes the actual tag down through
+// the 64 segment maps, and every lane walks its segment from the tag it was handed.
+__device__ __forceinline__ int walk_window(const uint8_t* win, uint8_t* segmap, uint8_t* entry, int lo, int np, int T,
+                                           int lane, int cur, int32_t* __restrict__ y) {
+    if (np <= 128) {
+        if (lane == 0) {
+            for (int r = np - 1; r >= 0; --r) {
+                cur = win[r * T + cur];
+                y[lo + r] = cur;
+            }
+            entry[64] = (uint8_t)cur;
+        }
+    } else {
+        int bot, top;
+        compose_segments(win, segmap, np, T, lane, bot, top);
+        __syncthreads();
+        if (lane == 0) {
+            for (int l = 63; l >= 0; --l) {
+                entry[l] = (uint8_t)cur;
+                cur = segmap[l * T + cur];
+            }
+            entry[64] = (uint8_t)cur;
+        }
+        __syncthreads();
+        int t = entry[lane];
+        for (int r = top - 1; r >= bot; --r) {
+            t = win[r * T + t];
+            y[lo + r] = t;
+        }
+    }
+    __syncthreads();
+    return entry[64];
+}
+
+// One wave per sequence: draws y_{L-1} from alpha_{L-1}, then follows the maps down through LDS
+// windows of the table, one after the other.
+template <int K>
+__global__ __launch_bounds__(64) void sample_walk_kernel(const int32_t* __restrict__ lengths, const float* __restrict__ ua,
+                                                         const float* __restrict__ uniforms, const uint8_t* __restrict__ F,
+                                                         int N, int T, int32_t* __restrict__ tags) {
+    __shared__ __attribute__((aligned(16))) uint8_t win[kWalkWindow];
+    __shared__ uint8_t segmap[64 * 256];
+    __shared__ uint8_t entry[65];
+    const int b = blockIdx.x, lane = threadIdx.x;
+    const int L = clamp_length(lengths, b, N);
+    int32_t* y = tags + (size_t)b * N;
+    for (int i = L + lane; i < N; i += 64) y[i] = -1;
+    if (L == 0) return;
+    const size_t vb = (size_t)b * N;
+    int cur = draw_last_tag<K>(ua + (vb + L - 1) * T, uniforms[vb + L - 1], T, lane);
+    if (cur < 0) {  // no finite path: all tags 0
+        for (int i = lane; i < L; i += 64) y[i] = 0;
+        return;
+    }
     if (lane == 0) y[L - 1] = cur;
-    // Positions L-2 .. 0 through LDS windows of the table.  A short window is walked by one lane.  A
-    // long one (small tag sets) is cut into 64 segments: every lane first composes the maps of its
-    // segment for all T possible tags above it (independent look-ups, so they overlap), one lane
-    // then passes the actual tag down through the 64 segment maps, and every lane walks its segment
-    // from the tag it was handed.
     const int wp = kWalkWindow / T;  // positions a window (T <= 256: at least 64)
     int hi = L - 1;                  // positions [0, hi) still to walk
     while (hi > 0) {
         const int lo = hi - wp > 0 ? hi - wp : 0;
-        const int np = hi - lo;
-        const uint8_t* src = F + (vb + lo) * T;
-        const int nbytes = np * T;
-        if (((reinterpret_cast<uintptr_t>(src) | (uintptr_t)nbytes) & 15) == 0) {
-            for (int k = lane; k < nbytes / 16; k += 64)
-                reinterpret_cast<uint4*>(win)[k] = reinterpret_cast<const uint4*>(src)[k];
-        } else {
-            for (int k = lane; k < nbytes; k += 64) win[k] = src[k];
-        }
+        load_window(win, F + vb * T, lo, hi - lo, T, lane);
         __syncthreads();
-        if (np <= 128) {
-            if (lane == 0) {
-                for (int i = hi - 1; i >= lo; --i) {
-                    cur = win[(i - lo) * T + cur];
-                    y[i] = cur;
-                }
-            }
-        } else {
-            const int seg = (np + 63) / 64;
-            const int bot = lane * seg < np ? lane * seg : np, top = bot + seg < np ? bot + seg : np;  // window-relative
-            for (int c0 = 0; c0 < T; c0 += 4) {
-                int t0 = c0, t1 = c0 + 1 < T ? c0 + 1 : c0, t2 = c0 + 2 < T ? c0 + 2 : c0, t3 = c0 + 3 < T ? c0 + 3 : c0;
-                for (int r = top - 1; r >= bot; --r) {
-                    const uint8_t* row = win + r * T;
-                    t0 = row[t0]; t1 = row[t1]; t2 = row[t2]; t3 = row[t3];
-                }
-                segmap[lane * T + c0] = (uint8_t)t0;
-                if (c0 + 1 < T) segmap[lane * T + c0 + 1] = (uint8_t)t1;
-                if (c0 + 2 < T) segmap[lane * T + c0 + 2] = (uint8_t)t2;
-                if (c0 + 3 < T) segmap[lane * T + c0 + 3] = (uint8_t)t3;
-            }
-            __syncthreads();
-            if (lane == 0) {
-                for (int l = 63; l >= 0; --l) {
-                    entry[l] = (uint8_t)cur;
-                    cur = segmap[l * T + cur];
-                }
-                entry[64] = (uint8_t)cur;
-            }
-            __syncthreads();
-            int t = entry[lane];
-            for (int r = top - 1; r >= bot; --r) {
-                t = win[r * T + t];
-                y[lo + r] = t;
-            }
-            cur = entry[64];
-        }
-        __syncthreads();
+        cur = walk_window(win, segmap, entry, lo, hi - lo, T, lane, cur, y);
         hi = lo;
     }
 }
 
+// Long sequences, all windows at once (W windows a sequence, counted from the top: window w holds the
+// positions below L - 1 - w wp).  First every window's maps are composed into one map of the tag above
+// the window to the tag of its lowest position (winmap [B][W][T] bytes) ...
+__global__ __launch_bounds__(64) void sample_window_map_kernel(const int32_t* __restrict__ lengths,
+                                                               const uint8_t* __restrict__ F, int N, int T, int W,
+                                                               uint8_t* __restrict__ winmap) {
+    __shared__ __attribute__((aligned(16))) uint8_t win[kWalkWindow];
+    __shared__ uint8_t segmap[64 * 256];
+    const int b = blockIdx.x / W, w = blockIdx.x % W, lane = threadIdx.x;
+    const int L = clamp_length(lengths, b, N);
+    const int wp = kWalkWindow / T;
+    const int hi = L - 1 - w * wp;
+    if (hi <= 0) return;
+    const int lo = hi - wp > 0 ? hi - wp : 0, np = hi - lo;
+    load_window(win, F + (size_t)b * N * T, lo, np, T, lane);
+    __syncthreads();
+    uint8_t* out = winmap + ((size_t)b * W + w) * T;
+    if (np <= 128) {
+        for (int t = lane; t < T; t += 64) {
+            int cur = t;
+            for (int r = np - 1; r >= 0; --r) cur = win[r * T + cur];
+            out[t] = (uint8_t)cur;
+        }
+    } else {
+        int bot, top;
+        compose_segments(win, segmap, np, T, lane, bot, top);
+        __syncthreads();
+        for (int t = lane; t < T; t += 64) {
+            int cur = t;
+            for (int l = 63; l >= 0; --l) cur = segmap[l * T + cur];
+            out[t] = (uint8_t)cur;
+        }
+    }
+}
+
+// ... then every window finds the tag above it by passing the tag of the last position through the
+// maps of the windows above (at most W look-ups in LDS) and walks its own positions.
+template <int K>
+__global__ __launch_bounds__(64) void sample_window_walk_kernel(const int32_t* __restrict__ lengths, const float* __restrict__ ua,
+                                                                const float* __restrict__ uniforms, const uint8_t* __restrict__ F,
+                                                                int N, int T, int W, const uint8_t* __restrict__ winmap,
+                                                                int32_t* __restrict__ tags) {
+    __shared__ __attribute__((aligned(16))) uint8_t win[kWalkWindow];
+    __shared__ uint8_t segmap[64 * 256];  // first the maps of the windows above (W T <= 16384 bytes)
+    __shared__ uint8_t entry[65];
+    const int b = blockIdx.x / W, w = blockIdx.x % W, lane = threadIdx.x;
+    const int L = clamp_length(lengths, b, N);
+    int32_t* y = tags + (size_t)b * N;
+    if (w == 0)
+        for (int i = L + lane; i < N; i += 64) y[i] = -1;
+    if (L == 0) return;
+    const size_t vb = (size_t)b * N;
+    const int wp = kWalkWindow / T;
+    const int hi = L - 1 - w * wp;
+    const int lo = hi - wp > 0 ? hi - wp : 0;
+    int cur = draw_last_tag<K>(ua + (vb + L - 1) * T, uniforms[vb + L - 1], T, lane);
+    if (cur < 0) {  // no finite path: all tags 0
+        if (w == 0 && lane == 0) y[L - 1] = 0;
+        for (int i = lo + lane; i < hi; i += 64) y[i] = 0;
+        return;
+    }
+    if (w == 0 && lane == 0) y[L - 1] = cur;
+    if (hi <= 0) return;
+    load_window(win, F + vb * T, lo, hi - lo, T, lane);
+    const uint8_t* above = winmap + (size_t)b * W * T;
+    for (int k = lane; k < w * T; k += 64) segmap[k] = above[k];
+    __syncthreads();
+    for (int v = 0; v < w; ++v) cur = segmap[v * T + cur];
+    __syncthreads();
+    walk_window(win, segmap, entry, lo, hi - lo, T, lane, cur, y);
+}
+
 template <typename TIN>
 static hipError_t launch_sample_T(const TIN* phi, const int32_t* lengths, const float* ua, const double* Oa,
-                                  const float* uniforms, int B, int N, int T, uint8_t* F, int32_t* tags, hipStream_t st) {
+                                  const float* uniforms, int B, int N, int T, uint8_t* F, uint8_t* winmap, int32_t* tags,
+                                  hipStream_t st) {
     if (N > 1) {
         const long long units = (long long)B * (N - 1);
         auto blocks = [&](int ppw) { return dim3((unsigned)((units + 4 * ppw - 1) / (4 * ppw))); };
@@ -707,6 +804,18 @@ static hipError_t launch_sample_T(const TIN* phi, const int32_t* lengths, const 
         const hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
+    // Several windows a sequence: all of them at once, two launches, if their maps fit the LDS staging.
+    const int wp = kWalkWindow / T, W = N > 1 ? (N - 1 + wp - 1) / wp : 1;
+    if (W >= 2 && (size_t)W * T <= 64 * 256 && winmap) {
+        hipLaunchKernelGGL(sample_window_map_kernel, dim3(B * W), dim3(64), 0, st, lengths, F, N, T, W, winmap);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+        const dim3 grid(B * W);
+        if (T <= 64) hipLaunchKernelGGL(sample_window_walk_kernel<1>, grid, dim3(64), 0, st, lengths, ua, uniforms, F, N, T, W, winmap, tags);
+        else if (T <= 128) hipLaunchKernelGGL(sample_window_walk_kernel<2>, grid, dim3(64), 0, st, lengths, ua, uniforms, F, N, T, W, winmap, tags);
+        else hipLaunchKernelGGL(sample_window_walk_kernel<4>, grid, dim3(64), 0, st, lengths, ua, uniforms, F, N, T, W, winmap, tags);
+        return hipGetLastError();
+    }
     if (T <= 64) hipLaunchKernelGGL(sample_walk_kernel<1>, dim3(B), dim3(64), 0, st, lengths, ua, uniforms, F, N, T, tags);
     else if (T <= 128) hipLaunchKernelGGL(sample_walk_kernel<2>, dim3(B), dim3(64), 0, st, lengths, ua, uniforms, F, N, T, tags);
     else hipLaunchKernelGGL(sample_walk_kernel<4>, dim3(B), dim3(64), 0, st, lengths, ua, uniforms, F, N, T, tags);
@@ -714,11 +823,19 @@ static hipError_t launch_sample_T(const TIN* phi, const int32_t* lengths, const 
 }
 
 // ua, Oa: alpha of every position from the forward pass ([B][N][T] normalised vectors, [B][N] offsets);
-// F: [B][N][T] bytes of scratch for the maps.
+// F: [B][N][T] bytes of scratch for the maps; winmap: sample_winmap_bytes(B, N, T) bytes of scratch for
+// the composed maps of the windows of long sequences (null: windows are walked one after the other).
+size_t sample_winmap_bytes(int B, int N, int T) {
+    const int wp = kWalkWindow / T;
+    return (size_t)B * ((N + wp - 1) / wp + 1) * T;
+}
+
 hipError_t launch_backward_sample(int dtype, const void* phi, const int32_t* lengths, const float* ua, const double* Oa,
-                                  const float* uniforms, int B, int N, int T, uint8_t* F, int32_t* tags, hipStream_t st) {
-    if (dtype == 0) return launch_sample_T(static_cast<const float*>(phi), lengths, ua, Oa, uniforms, B, N, T, F, tags, st);
-    return launch_sample_T(static_cast<const uint16_t*>(phi), lengths, ua, Oa, uniforms, B, N, T, F, tags, st);
+                                  const float* uniforms, int B, int N, int T, uint8_t* F, uint8_t* winmap, int32_t* tags,
+                                  hipStream_t st) {
+    if (dtype == 0)
+        return launch_sample_T(static_cast<const float*>(phi), lengths, ua, Oa, uniforms, B, N, T, F, winmap, tags, st);
+    return launch_sample_T(static_cast<const uint16_t*>(phi), lengths, ua, Oa, uniforms, B, N, T, F, winmap, tags, st);
 }
 
 }  // namespace lccrf
