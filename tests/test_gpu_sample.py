@@ -105,6 +105,21 @@ def test_sample_long_chains(crf, oracle_mod, T, N):
     _check_every_draw(crf, oracle_mod, phi, lens, 200 + T, f"long T={T} N={N}")
 
 
+@pytest.mark.parametrize("T,N", [(4, 13000), (16, 2500), (130, 400), (200, 300)])
+def test_sample_many_windows_edge_lengths(crf, oracle_mod, T, N):
+    """Sequences of several windows walked all at once: with empty and one-position sequences, lengths
+    that end inside the first window or exactly on a window boundary, and a chain without a finite path."""
+    wp = 16384 // T
+    phi, lens = workloads.random_case(8500 + T, 7, N, T, scale=1.5, ragged=True, min_len=N // 3)
+    lens[0], lens[1], lens[2], lens[3], lens[4] = 0, 1, 2, min(N, wp + 1), min(N, 2 * wp + 1)
+    _check_every_draw(crf, oracle_mod, phi, lens, 300 + T, f"windows T={T} N={N}")
+    phi[5, N // 2, :, :] = float("-inf")
+    got = crf.lccrf_sample(phi.cuda(), torch.rand(7, N).cuda(), lens.cuda()).cpu().numpy()
+    L5 = int(lens[5])
+    if L5 > N // 2:
+        assert (got[5, :L5] == 0).all() and (got[5, L5:] == -1).all()
+
+
 def test_sample_config5(crf, oracle_mod):
     w = workloads.WORKLOADS["cfg5"]
     _check_every_draw(crf, oracle_mod, workloads.phi_batch(w), workloads.lengths(w), 12, "cfg5")
