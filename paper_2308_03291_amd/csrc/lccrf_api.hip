@@ -529,6 +529,6 @@ int lccrf_set_scan_chunk(int chunk) {
     return LCCRF_OK;
 }
 
-int lccrf_version(void) { return 106; }
+int lccrf_version(void) { return 107; }
 
 }  // extern "C"
