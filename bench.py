@@ -180,9 +180,10 @@ def main():
 
     value = pots / (ms_per_step * 1e-3)
     call_bytes = eff_pots * (2 * esz + 4)
-    if crf.auto_algo(crf.OP_MARGINALS, w.B, w.N, w.T) == crf.ALGO_SCAN:
+    if crf.auto_algo(crf.OP_MARGINALS, w.B, w.N, w.T) == crf.ALGO_SCAN or (w.T <= 32 and 2 <= w.N <= 65):
         # Chunked scan: the interval after the boundary phases is one kernel that makes both passes over
-        # every chunk (two reads of phi, the second from cache at best, and one write of mu).
+        # every chunk (two reads of phi, the second from cache at best, and one write of mu).  Sequences of
+        # at most 65 positions over at most 32 tags take the same kernel whole.
         kernel, alg_bytes = "wave_chunk_kernel", call_bytes
     else:
         # dominant kernel: second pass = one read of phi + one write of mu over the positions in the chains.

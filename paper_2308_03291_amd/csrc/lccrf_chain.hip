@@ -942,6 +942,14 @@ hipError_t launch_sequential_sum(int op, int dtype, const void* phi, const int32
     a.emit = emit;
     a.trans = trans;
     if (emit && T > 64) return hipErrorInvalidValue;  // the caller checks structured_supported(T) first
+    if (wave_supported(T) && op == 1 && !emit && wave_chunks_fused(N - 1)) {
+        // Short sequences: both passes in one launch, the vectors in LDS (as for the chunks of the scan).
+        if (between) {
+            const hipError_t e = hipEventRecord(between, st);
+            if (e != hipSuccess) return e;
+        }
+        return launch_wave_chunks(dtype, a, st);
+    }
     if (wave_supported(T)) return launch_wave(op, dtype, a, st, between);
     if (emit) return (T % 4) == 0 ? launch_structured_64<true>(op, a, st, between) : launch_structured_64<false>(op, a, st, between);
     // Pairs pay off when one workgroup per chain would leave at least half of the chip idle.
