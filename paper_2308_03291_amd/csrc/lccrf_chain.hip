@@ -950,6 +950,13 @@ hipError_t launch_sequential_sum(int op, int dtype, const void* phi, const int32
         }
         return launch_wave_chunks(dtype, a, st);
     }
+    if (wave_supported(T) && op == 0 && !emit) {
+        if (between) {
+            const hipError_t e = hipEventRecord(between, st);
+            if (e != hipSuccess) return e;
+        }
+        return launch_wave_logz(dtype, a, st);
+    }
     if (wave_supported(T)) return launch_wave(op, dtype, a, st, between);
     if (emit) return (T % 4) == 0 ? launch_structured_64<true>(op, a, st, between) : launch_structured_64<false>(op, a, st, between);
     // Pairs pay off when one workgroup per chain would leave at least half of the chip idle.

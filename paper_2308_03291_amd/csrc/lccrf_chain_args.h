@@ -99,6 +99,7 @@ bool wave_supported(int T);
 hipError_t launch_wave_pass(bool second_pass, int dtype, const ChainArgs& a, hipStream_t st);
 // Chunked schedule with chunks short enough (wave_chunks_fused): both passes of every chunk in one
 // launch, one workgroup of two waves per chunk, the chunk's vectors in LDS (ua, ub, Oa, Ob unused).
+hipError_t launch_wave_logz(int dtype, const ChainArgs& a, hipStream_t st);  // whole sequences, logZ only, one launch
 bool wave_chunks_fused(int chunk);
 hipError_t launch_wave_chunks(int dtype, const ChainArgs& a, hipStream_t st);
 

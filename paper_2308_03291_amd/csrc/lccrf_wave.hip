@@ -329,7 +329,8 @@ __device__ __forceinline__ VecStore device_vectors(const ChainArgs& a, int b) {
     return VecStore{a.ua + vb * a.T, a.ub + vb * a.T, a.Oa + vb, a.Ob + vb, 0};
 }
 
-template <int TP, typename TIN, bool ALIGNED, bool WITH_H, bool STRUCT, int PF = wave_ring_depth(TP, false)>
+// MEET_ONLY: only the vectors of the meeting position are stored (all a log-partition needs).
+template <int TP, typename TIN, bool ALIGNED, bool WITH_H, bool STRUCT, int PF = wave_ring_depth(TP, false), bool MEET_ONLY = false>
 __device__ __forceinline__ void wave_half_body(const ChainArgs& a, const Span& sp, int dir, int lane, const VecStore& vs) {
     using W = WGeo<TP>;
     constexpr int R = W::R;
@@ -374,7 +375,7 @@ __device__ __forceinline__ void wave_half_body(const ChainArgs& a, const Span& s
             O += (double)d;
 #pragma unroll
             for (int j = 0; j < 4; ++j) vc[j] -= d;
-            if (WITH_H && pos != h) return d;  // an entropy query needs the vectors of the meeting position only
+            if ((WITH_H || MEET_ONLY) && pos != h) return d;  // an entropy query needs the vectors of the meeting position only
             if (rg == 0) {
 #pragma unroll
                 for (int j = 0; j < 4; ++j)
@@ -415,7 +416,7 @@ __device__ __forceinline__ void wave_half_body(const ChainArgs& a, const Span& s
             O += (double)d;
 #pragma unroll
             for (int k = 0; k < R; ++k) vr[k] -= d;
-            if (WITH_H && pos != h) return d;
+            if ((WITH_H || MEET_ONLY) && pos != h) return d;
             if (cg == 0) {
 #pragma unroll
                 for (int k = 0; k < R; ++k)
@@ -665,8 +666,54 @@ __global__ __launch_bounds__(128) void wave_chunk_kernel(ChainArgs a) {
     wave_marginal_body<TP, TIN, ALIGNED, false, ENT>(a, sp, dir, lane, vs);
 }
 
+// The log-partition of whole sequences in one launch: the two half chains of a sequence as the two
+// waves of a workgroup, their vectors at the meeting position in LDS, combined by the first wave.
+template <int TP, typename TIN, bool ALIGNED>
+__global__ __launch_bounds__(128) void wave_logz_kernel(ChainArgs a) {
+    __shared__ float sua[TP], sub[TP];
+    __shared__ double sO[2];
+    const int lane = threadIdx.x & 63, dir = threadIdx.x >> 6;
+    const Span sp = make_span(a, blockIdx.x);
+    const int b = sp.b, T = a.T, L = sp.L;
+    if (L == 0) {
+        if (threadIdx.x == 0 && a.logZ) a.logZ[b] = 0.f;
+        if (threadIdx.x == 0 && a.logZ64) a.logZ64[b] = 0.0;
+        return;
+    }
+    const VecStore vs{sua, sub, &sO[0], &sO[1], meeting_point(sp.p0, sp.e)};
+    wave_half_body<TP, TIN, ALIGNED, false, false, wave_ring_depth(TP, false), true>(a, sp, dir, lane, vs);
+    __syncthreads();
+    if (dir == 0) {
+        const float z = lane < T ? sua[lane] + sub[lane] : LCCRF_NEG_INF;
+        const float m = xor_max<1, 64>(z);
+        const float S = xor_sum<1, 64>(ex2(z - finite_or_zero(m)));
+        const double lz = ((double)(m + lg2(S)) + sO[0] + sO[1]) * kLn2;
+        if (lane == 0 && a.logZ) a.logZ[b] = (float)lz;
+        if (lane == 0 && a.logZ64) a.logZ64[b] = lz;
+    }
+}
+
 // ---------------------------------------------------------------------------------------
 bool wave_supported(int T) { return T >= 1 && T <= 32; }
+
+template <int TP>
+static hipError_t launch_wave_logz_tp(int dtype, const ChainArgs& a, hipStream_t st) {
+    const dim3 grid(a.B), block(128);
+    const bool aligned = (a.T % 4) == 0;
+    if (dtype == 0) {
+        if (aligned) hipLaunchKernelGGL((wave_logz_kernel<TP, float, true>), grid, block, 0, st, a);
+        else hipLaunchKernelGGL((wave_logz_kernel<TP, float, false>), grid, block, 0, st, a);
+    } else {
+        if (aligned) hipLaunchKernelGGL((wave_logz_kernel<TP, uint16_t, true>), grid, block, 0, st, a);
+        else hipLaunchKernelGGL((wave_logz_kernel<TP, uint16_t, false>), grid, block, 0, st, a);
+    }
+    return hipGetLastError();
+}
+
+// logZ (a.logZ and/or a.logZ64) of whole sequences, plain potentials, T <= 32.
+hipError_t launch_wave_logz(int dtype, const ChainArgs& a, hipStream_t st) {
+    return a.T <= 16 ? launch_wave_logz_tp<16>(dtype, a, st) : launch_wave_logz_tp<32>(dtype, a, st);
+}
 bool wave_chunks_fused(int chunk) { return chunk >= 1 && chunk <= kFusedChunk; }
 
 template <int TP, typename TIN, bool ALIGNED>
