@@ -254,8 +254,9 @@ int lccrf_argmax_structured(const float* emit, const float* trans, const int32_t
                             int B, int N, int T, float* best_score, int32_t* tags,
                             void* workspace, size_t workspace_bytes, void* stream);
 
-/* Positions per chunk of LCCRF_ALGO_SCAN: a process-wide tuning knob (default 32; 0 restores the
- * default; values outside [4, 4096] return LCCRF_EINVAL and change nothing).  It enters
+/* Positions per chunk of LCCRF_ALGO_SCAN: a process-wide tuning knob.  0 (the default) lets every
+ * call choose by its shape (8, 16 or 32: the shortest chunks that the chip still holds all at
+ * once); other values outside [4, 4096] return LCCRF_EINVAL and change nothing.  It enters
  * lccrf_workspace_bytes, so set it before sizing a workspace, and not while another thread is
  * inside a query.  Results do not depend on it beyond rounding. */
 int lccrf_set_scan_chunk(int chunk);

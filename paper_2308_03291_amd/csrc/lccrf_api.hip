@@ -9,8 +9,18 @@ constexpr size_t kAlign = 256;
 inline size_t round_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 
 // Positions per chunk of the chunked scan (lccrf_set_scan_chunk).
-constexpr int kDefaultScanChunk = 32;
-int g_scan_chunk = kDefaultScanChunk;
+// Positions per chunk of the scan.  0: chosen by shape, the smallest of 8, 16 and 32 that keeps the
+// chunks of the batch (one wave each in the scan's first phase) within what the chip holds at once
+// (measured: short chunks win, 8 by 2.8 times on the marginals of B=1, N=128, T=32 against the
+// sequential schedule, until the chunks outnumber the SIMDs, resp. twice their number at 16 tags).
+int g_scan_chunk_user = 0;
+inline int scan_chunk(long long B, long long N, long long T) {
+    if (g_scan_chunk_user) return g_scan_chunk_user;
+    const long long cap = T > 16 ? 1024 : 2048;
+    for (int c = 8; c < 32; c *= 2)
+        if (B * ((N + c - 1) / c) <= cap) return c;
+    return 32;
+}
 
 struct SumWorkspace {
     size_t ua, ub, Oa, Ob, mail, failed;
@@ -24,6 +34,7 @@ struct SumWorkspace {
 inline SumWorkspace sum_workspace(size_t B, size_t N, size_t T) {
     SumWorkspace w;
     size_t off = 0;
+    const size_t g_scan_chunk = (size_t)scan_chunk((long long)B, (long long)N, (long long)T);
     w.ua = off; off += round_up(B * N * T * sizeof(float));
     w.ub = off; off += round_up(B * N * T * sizeof(float));
     w.Oa = off; off += round_up(B * N * sizeof(double));
@@ -69,6 +80,7 @@ struct MaxWorkspace {
 inline MaxWorkspace max_workspace(size_t B, size_t N, size_t T) {
     MaxWorkspace w;
     size_t off = 0;
+    const size_t g_scan_chunk = (size_t)scan_chunk((long long)B, (long long)N, (long long)T);
     w.bp = off; off += round_up(B * N * T);
     const size_t BC = lccrf::scan_supported_max((int)T) ? B * ((N + g_scan_chunk - 1) / g_scan_chunk) : 0;
     w.mid = off; off += round_up((BC > B ? BC : B) * 2 * T * sizeof(double));
@@ -112,21 +124,27 @@ int check_common(const void* phi, int dt, int B, int N, int T, const void* ws, s
 }
 
 // Whether LCCRF_ALGO_AUTO takes the chunked scan: the tag set fits its kernels, the chains are long
-// enough for the serial depth to dominate, and the batch alone would not fill the chip.  Measured
-// for up to 16 tags: the sequential schedule costs about 0.67 us a position of the longest chain
-// whatever the batch (up to a few waves per SIMD), the scan about 50 us plus 1.1 ns a position of
-// the whole batch, which crosses near 450 sequences for every length from 256 up.  For 17 .. 32
-// tags (sum queries only) a chunk product costs eight times the matrix instructions: the scan wins
-// up to about 32768 positions a batch (the paper's own benchmark size, 128 x 256, is the limit).
-inline bool scan_pays(int B, int N, int T) { return lccrf::scan_supported_max(T) && N >= 8 * g_scan_chunk && B <= 448; }
+// enough for the serial depth to dominate (eight chunks; with the chunk chosen by shape that is 64
+// positions in small batches), and the batch alone would not fill the chip.  Measured, sum queries:
+// with up to 16 tags the sequential schedule costs about 0.3 to 0.6 us a position of the longest
+// chain whatever the batch (up to a few waves per SIMD), the scan some 15 us plus 1 ns a position of
+// the whole batch, which cross near 450 sequences; with 17 .. 32 tags a chunk product costs eight
+// times the matrix instructions and the scan wins up to about 32768 positions a batch (the paper's
+// own benchmark size, 128 x 256, is the limit).
 inline bool scan_pays_sum(int B, int N, int T) {
-    if (scan_pays(B, N, T)) return true;
-    return lccrf::scan_supported(T) && N >= 8 * g_scan_chunk && (long long)B * N <= 32768;
+    if (!lccrf::scan_supported(T) || N < 8 * scan_chunk(B, N, T)) return false;
+    return T <= 16 ? B <= 448 : (long long)B * N <= 32768;
+}
+// The max-plus scan (16 tags at most) pays its chunk products in double-precision vector
+// instructions: it takes chains twice as long to pay, and at most 65536 positions a batch
+// (B=256, N=256: 86 us against 62 sequential; B=128, N=512: 87 against 114).
+inline bool scan_pays_max(int B, int N, int T) {
+    return lccrf::scan_supported_max(T) && N >= 16 * scan_chunk(B, N, T) && (long long)B * N <= 65536;
 }
 // The entropy-like queries make two passes under the scan against one sequential pass: with 17 .. 32
 // tags it takes chains twice as long to pay.
 inline bool scan_pays_entropy(int B, int N, int T) {
-    return scan_pays(B, N, T) || (scan_pays_sum(B, N, T) && N >= 16 * g_scan_chunk);
+    return scan_pays_sum(B, N, T) && (T <= 16 || N >= 16 * scan_chunk(B, N, T));
 }
 
 int sum_query(int op, const void* phi, int dt, const int32_t* lengths, int B, int N, int T, float* logZ,
@@ -150,7 +168,7 @@ int sum_query(int op, const void* phi, int dt, const int32_t* lengths, int B, in
         double* OF = reinterpret_cast<double*>(base + w.OF);
         float* Gv = reinterpret_cast<float*>(base + w.Gv);
         double* OG = reinterpret_cast<double*>(base + w.OG);
-        hipError_t e = lccrf::launch_scan_boundaries(dt, phi, lengths, B, N, T, g_scan_chunk,
+        hipError_t e = lccrf::launch_scan_boundaries(dt, phi, lengths, B, N, T, scan_chunk(B, N, T),
                                                      reinterpret_cast<float*>(base + w.Pl),
                                                      reinterpret_cast<float*>(base + w.rel),
                                                      reinterpret_cast<double*>(base + w.base), Fv, OF, Gv, OG,
@@ -159,7 +177,7 @@ int sum_query(int op, const void* phi, int dt, const int32_t* lengths, int B, in
             e = lccrf::launch_chunked_marginals(dt, phi, lengths, B, N, T, reinterpret_cast<float*>(base + w.ua),
                                                 reinterpret_cast<float*>(base + w.ub),
                                                 reinterpret_cast<double*>(base + w.Oa),
-                                                reinterpret_cast<double*>(base + w.Ob), marginals, g_scan_chunk, Fv,
+                                                reinterpret_cast<double*>(base + w.Ob), marginals, scan_chunk(B, N, T), Fv,
                                                 OF, Gv, OG, st, static_cast<hipEvent_t>(ev_between), false);
         if (e != hipSuccess) return LCCRF_ELAUNCH;
         if (ev_end && hipEventRecord(static_cast<hipEvent_t>(ev_end), st) != hipSuccess) return LCCRF_ELAUNCH;
@@ -202,7 +220,7 @@ int lccrf_auto_algo(lccrf_op op, int B, int N, int T) {
         case LCCRF_OP_MARGINALS:
         case LCCRF_OP_LOG_PROB:
         case LCCRF_OP_SAMPLE: scan = scan_pays_sum(B, N, T); break;
-        case LCCRF_OP_ARGMAX: scan = scan_pays(B, N, T); break;
+        case LCCRF_OP_ARGMAX: scan = scan_pays_max(B, N, T); break;
         case LCCRF_OP_ENTROPY:
         case LCCRF_OP_CROSS_ENTROPY: scan = scan_pays_entropy(B, N, T); break;
         default: return LCCRF_EINVAL;
@@ -243,15 +261,15 @@ int lccrf_argmax_algo(const void* phi, lccrf_dtype dt, const int32_t* lengths, i
     uint8_t* bp = reinterpret_cast<uint8_t*>(base + w.bp);
     double* mid = reinterpret_cast<double*>(base + w.mid);
     hipError_t e;
-    if (algo == LCCRF_ALGO_SCAN || (algo == LCCRF_ALGO_AUTO && scan_pays(B, N, T))) {
+    if (algo == LCCRF_ALGO_SCAN || (algo == LCCRF_ALGO_AUTO && scan_pays_max(B, N, T))) {
         int32_t* pin = reinterpret_cast<int32_t*>(base + w.pin);
-        e = lccrf::launch_scan_pins(dt, phi, lengths, B, N, T, g_scan_chunk, reinterpret_cast<double*>(base + w.Mx),
+        e = lccrf::launch_scan_pins(dt, phi, lengths, B, N, T, scan_chunk(B, N, T), reinterpret_cast<double*>(base + w.Mx),
                                     reinterpret_cast<uint8_t*>(base + w.K), pin,
                                     {reinterpret_cast<double*>(base + w.Mx2), reinterpret_cast<uint8_t*>(base + w.K2),
                                      reinterpret_cast<int32_t*>(base + w.pin2)},
                                     best_score, st);
         if (e == hipSuccess)
-            e = lccrf::launch_chunked_max(dt, phi, lengths, B, N, T, bp, mid, tags, g_scan_chunk, pin, st);
+            e = lccrf::launch_chunked_max(dt, phi, lengths, B, N, T, bp, mid, tags, scan_chunk(B, N, T), pin, st);
     } else {
         e = lccrf::launch_sequential_max(dt, phi, lengths, B, N, T, bp, mid, best_score, tags, st);
     }
@@ -282,7 +300,7 @@ static hipError_t launch_log_partition64(const void* phi, int dt, const int32_t*
     double* lz64 = reinterpret_cast<double*>(base + w.lz64);
     if (scan_pays_sum(B, N, T))
         return lccrf::launch_scan_boundaries(
-            dt, phi, lengths, B, N, T, g_scan_chunk, reinterpret_cast<float*>(base + w.Pl),
+            dt, phi, lengths, B, N, T, scan_chunk(B, N, T), reinterpret_cast<float*>(base + w.Pl),
             reinterpret_cast<float*>(base + w.rel), reinterpret_cast<double*>(base + w.base),
             reinterpret_cast<float*>(base + w.Fv), reinterpret_cast<double*>(base + w.OF),
             reinterpret_cast<float*>(base + w.Gv), reinterpret_cast<double*>(base + w.OG), group_buffers(w, base),
@@ -329,7 +347,7 @@ int lccrf_entropy(const void* phi, lccrf_dtype dt, const int32_t* lengths, int B
         double* OG = reinterpret_cast<double*>(base + w.OG);
         float* ent = reinterpret_cast<float*>(base + w.ent);
         float* lzf = reinterpret_cast<float*>(base + w.lzf);
-        hipError_t e = lccrf::launch_scan_boundaries(dt, phi, lengths, B, N, T, g_scan_chunk,
+        hipError_t e = lccrf::launch_scan_boundaries(dt, phi, lengths, B, N, T, scan_chunk(B, N, T),
                                                      reinterpret_cast<float*>(base + w.Pl),
                                                      reinterpret_cast<float*>(base + w.rel),
                                                      reinterpret_cast<double*>(base + w.base), Fv, OF, Gv, OG,
@@ -338,9 +356,9 @@ int lccrf_entropy(const void* phi, lccrf_dtype dt, const int32_t* lengths, int B
             e = lccrf::launch_chunked_marginals(dt, phi, lengths, B, N, T, reinterpret_cast<float*>(base + w.ua),
                                                 reinterpret_cast<float*>(base + w.ub),
                                                 reinterpret_cast<double*>(base + w.Oa),
-                                                reinterpret_cast<double*>(base + w.Ob), nullptr, g_scan_chunk, Fv, OF,
+                                                reinterpret_cast<double*>(base + w.Ob), nullptr, scan_chunk(B, N, T), Fv, OF,
                                                 Gv, OG, st, nullptr, false, ent);
-        if (e == hipSuccess) e = lccrf::launch_entropy_reduce(ent, lengths, lzf, B, N, g_scan_chunk, entropy, st);
+        if (e == hipSuccess) e = lccrf::launch_entropy_reduce(ent, lengths, lzf, B, N, scan_chunk(B, N, T), entropy, st);
         return e == hipSuccess ? LCCRF_OK : LCCRF_ELAUNCH;
     }
     const hipError_t e = lccrf::launch_entropy(
@@ -374,7 +392,7 @@ static int cross_query(bool kl, const void* phi_p, const void* phi_q, lccrf_dtyp
         float* ent = reinterpret_cast<float*>(base + w.ent);
         double* lzp = reinterpret_cast<double*>(base + w.hoff);
         if (e == hipSuccess)
-            e = lccrf::launch_scan_boundaries(dt, phi_p, lengths, B, N, T, g_scan_chunk,
+            e = lccrf::launch_scan_boundaries(dt, phi_p, lengths, B, N, T, scan_chunk(B, N, T),
                                               reinterpret_cast<float*>(base + w.Pl), reinterpret_cast<float*>(base + w.rel),
                                               reinterpret_cast<double*>(base + w.base), Fv, OF, Gv, OG,
                                               group_buffers(w, base), nullptr, true, st, lzp);
@@ -382,11 +400,11 @@ static int cross_query(bool kl, const void* phi_p, const void* phi_q, lccrf_dtyp
             e = lccrf::launch_chunked_marginals(dt, phi_p, lengths, B, N, T, reinterpret_cast<float*>(base + w.ua),
                                                 reinterpret_cast<float*>(base + w.ub),
                                                 reinterpret_cast<double*>(base + w.Oa),
-                                                reinterpret_cast<double*>(base + w.Ob), nullptr, g_scan_chunk, Fv, OF,
+                                                reinterpret_cast<double*>(base + w.Ob), nullptr, scan_chunk(B, N, T), Fv, OF,
                                                 Gv, OG, st, nullptr, false, ent, phi_q, kl);
         if (e == hipSuccess)
             e = lccrf::launch_cross_reduce(kl, ent, lengths, reinterpret_cast<const double*>(base + w.lz64), lzp, B, N,
-                                           g_scan_chunk, out, st);
+                                           scan_chunk(B, N, T), out, st);
         return e == hipSuccess ? LCCRF_OK : LCCRF_ELAUNCH;
     }
     if (e == hipSuccess)
@@ -437,12 +455,12 @@ int lccrf_sample(const void* phi, lccrf_dtype dt, const int32_t* lengths, const 
     if (scan_pays_sum(B, N, T)) {  // alpha everywhere, chunk by chunk from the scan's boundary vectors
         float* Fv = reinterpret_cast<float*>(base + w.Fv);
         double* OF = reinterpret_cast<double*>(base + w.OF);
-        e = lccrf::launch_scan_boundaries(dt, phi, lengths, B, N, T, g_scan_chunk, reinterpret_cast<float*>(base + w.Pl),
+        e = lccrf::launch_scan_boundaries(dt, phi, lengths, B, N, T, scan_chunk(B, N, T), reinterpret_cast<float*>(base + w.Pl),
                                           reinterpret_cast<float*>(base + w.rel), reinterpret_cast<double*>(base + w.base),
                                           Fv, OF, reinterpret_cast<float*>(base + w.Gv),
                                           reinterpret_cast<double*>(base + w.OG), group_buffers(w, base), nullptr, false, st);
         if (e == hipSuccess)
-            e = lccrf::launch_chunked_full_forward(dt, phi, lengths, B, N, T, ua, ub, Oa, Ob, g_scan_chunk, Fv, OF, st);
+            e = lccrf::launch_chunked_full_forward(dt, phi, lengths, B, N, T, ua, ub, Oa, Ob, scan_chunk(B, N, T), Fv, OF, st);
     } else {
         e = lccrf::launch_full_forward(dt, phi, lengths, B, N, T, ua, ub, Oa, Ob, st);
     }
@@ -523,9 +541,8 @@ const char* lccrf_strerror(int code) {
 }
 
 int lccrf_set_scan_chunk(int chunk) {
-    if (chunk == 0) chunk = kDefaultScanChunk;
-    if (chunk < 4 || chunk > 4096) return LCCRF_EINVAL;
-    g_scan_chunk = chunk;
+    if (chunk != 0 && (chunk < 4 || chunk > 4096)) return LCCRF_EINVAL;
+    g_scan_chunk_user = chunk;
     return LCCRF_OK;
 }
 

@@ -61,7 +61,11 @@ def test_auto_schedule_is_reported_without_a_gpu(lib):
     assert binding.auto_algo(binding.OP_MARGINALS, 128, 256, 32) == binding.ALGO_SCAN        # the paper's size
     assert binding.auto_algo(binding.OP_ARGMAX, 128, 256, 32) == binding.ALGO_SEQUENTIAL     # max-plus scan: 16 tags
     assert binding.auto_algo(binding.OP_ENTROPY, 128, 256, 32) == binding.ALGO_SEQUENTIAL
-    assert binding.auto_algo(binding.OP_MARGINALS, 32, 64, 32) == binding.ALGO_SEQUENTIAL    # config 2
+    assert binding.auto_algo(binding.OP_MARGINALS, 32, 64, 32) == binding.ALGO_SCAN          # config 2: chunks of 8
+    assert binding.auto_algo(binding.OP_MARGINALS, 32, 63, 32) == binding.ALGO_SEQUENTIAL    # fewer than eight chunks
+    assert binding.auto_algo(binding.OP_ARGMAX, 256, 256, 16) == binding.ALGO_SEQUENTIAL
+    assert binding.auto_algo(binding.OP_MARGINALS, 256, 256, 16) == binding.ALGO_SCAN
+    assert binding.auto_algo(binding.OP_MARGINALS, 4, 8, 5) == binding.ALGO_SEQUENTIAL       # config 1
     with pytest.raises(binding.LccrfError):
         binding.auto_algo(binding.OP_MARGINALS, 1, 8, 0)
     with pytest.raises(binding.LccrfError):
