@@ -34,14 +34,14 @@ struct SumWorkspace {
 inline SumWorkspace sum_workspace(size_t B, size_t N, size_t T) {
     SumWorkspace w;
     size_t off = 0;
-    const size_t g_scan_chunk = (size_t)scan_chunk((long long)B, (long long)N, (long long)T);
+    const size_t chunk = (size_t)scan_chunk((long long)B, (long long)N, (long long)T);
     w.ua = off; off += round_up(B * N * T * sizeof(float));
     w.ub = off; off += round_up(B * N * T * sizeof(float));
     w.Oa = off; off += round_up(B * N * sizeof(double));
     w.Ob = off; off += round_up(B * N * sizeof(double));
     w.mail = off; off += round_up(lccrf::pair_mail_words((int)B) * sizeof(unsigned long long));
     w.failed = off; off += round_up(B * sizeof(int));
-    const size_t BC = lccrf::scan_supported((int)T) ? B * ((N + g_scan_chunk - 1) / g_scan_chunk) : 0;
+    const size_t BC = lccrf::scan_supported((int)T) ? B * ((N + chunk - 1) / chunk) : 0;
     const size_t TP = (size_t)lccrf::scan_padded_tags((int)T);
     w.Pl = off; off += round_up(BC * TP * TP * sizeof(float));
     w.rel = off; off += round_up(BC * TP * sizeof(float));
@@ -50,7 +50,7 @@ inline SumWorkspace sum_workspace(size_t B, size_t N, size_t T) {
     w.OF = off; off += round_up(BC * sizeof(double));
     w.Gv = off; off += round_up(BC * T * sizeof(float));
     w.OG = off; off += round_up(BC * sizeof(double));
-    const size_t C = (N + g_scan_chunk - 1) / g_scan_chunk;
+    const size_t C = (N + chunk - 1) / chunk;
     const size_t gs = BC ? (size_t)lccrf::scan_group_size((int)C) : 0;
     const size_t BG = gs ? B * ((C + gs - 1) / gs) : 0;
     w.Pl2 = off; off += round_up(BG * TP * TP * sizeof(float));
@@ -80,14 +80,14 @@ struct MaxWorkspace {
 inline MaxWorkspace max_workspace(size_t B, size_t N, size_t T) {
     MaxWorkspace w;
     size_t off = 0;
-    const size_t g_scan_chunk = (size_t)scan_chunk((long long)B, (long long)N, (long long)T);
+    const size_t chunk = (size_t)scan_chunk((long long)B, (long long)N, (long long)T);
     w.bp = off; off += round_up(B * N * T);
-    const size_t BC = lccrf::scan_supported_max((int)T) ? B * ((N + g_scan_chunk - 1) / g_scan_chunk) : 0;
+    const size_t BC = lccrf::scan_supported_max((int)T) ? B * ((N + chunk - 1) / chunk) : 0;
     w.mid = off; off += round_up((BC > B ? BC : B) * 2 * T * sizeof(double));
     w.Mx = off; off += round_up(BC * 256 * sizeof(double));
     w.K = off; off += round_up(BC * 16);
     w.pin = off; off += round_up(BC * sizeof(int32_t));
-    const size_t C = (N + g_scan_chunk - 1) / g_scan_chunk;
+    const size_t C = (N + chunk - 1) / chunk;
     const size_t gs = BC ? (size_t)lccrf::scan_group_size((int)C) : 0;
     const size_t BG = gs ? B * ((C + gs - 1) / gs) : 0;
     w.Mx2 = off; off += round_up(BG * 256 * sizeof(double));
