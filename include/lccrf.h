@@ -84,7 +84,8 @@ typedef enum {
     LCCRF_EWORKSPACE = -3, /* workspace NULL or smaller than lccrf_workspace_bytes */
     LCCRF_EALIGN = -4,     /* phi, an output or the workspace is misaligned */
     LCCRF_ELAUNCH = -5,    /* the HIP runtime refused a launch */
-    LCCRF_ENOTIMPL = -6    /* the requested algo does not exist for this shape */
+    LCCRF_ENOTIMPL = -6,   /* the requested algo does not exist for this shape */
+    LCCRF_ETOOBIG = -7     /* lccrf_marginals_static: the shape needs more than the built-in scratch */
 } lccrf_status;
 
 /* Bytes of device scratch the given query needs (a multiple of 256); 0 on invalid
@@ -129,6 +130,25 @@ int lccrf_argmax(const void* phi, lccrf_dtype dt, const int32_t* lengths,
                  int B, int N, int T,
                  float* best_score, int32_t* tags,
                  void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * lccrf_marginals for callers that cannot allocate device memory or bring a workspace: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same inputs, outputs, results
+ * and errors as lccrf_marginals, but the scratch is a buffer built into the library
+ * (lccrf_static_scratch_bytes() bytes, 64 MiB, on every GPU the library runs on, held until the
+ * process ends); the call allocates and frees nothing.
+ *   - A shape whose lccrf_workspace_bytes(LCCRF_OP_MARGINALS, ...) exceeds that size is refused with
+ *     LCCRF_ETOOBIG before anything is enqueued (the headline shape B=64, N=512, T=128 needs 39 MB).
+ *   - Every call on one GPU uses that GPU's one buffer: calls that may overlap in time on the same
+ *     GPU (two streams, two threads) race and must not be made; calls on one stream are ordered.
+ *     Nothing in the buffer has to be cleared between calls: every kernel writes what it later reads.
+ *   - The first call on a device looks the buffer's address up (hipGetSymbolAddress); make it
+ *     outside a stream capture.  LCCRF_ELAUNCH if that lookup fails.
+ */
+size_t lccrf_static_scratch_bytes(void);
+int lccrf_marginals_static(const void* phi, lccrf_dtype dt, const int32_t* lengths,
+                           int B, int N, int T,
+                           float* logZ, float* marginals, void* stream);
 
 /* The same three queries with the schedule chosen by the caller (tests, benchmarks).
  * LCCRF_ENOTIMPL if `algo` is not available for the shape. */

@@ -33,7 +33,7 @@ EXPORTS = (
     "lccrf_marginals_timed", "lccrf_log_prob", "lccrf_entropy", "lccrf_cross_entropy", "lccrf_kl_divergence",
     "lccrf_sample", "lccrf_semi_markov_log_partition", "lccrf_log_partition_structured",
     "lccrf_marginals_structured", "lccrf_argmax_structured", "lccrf_set_scan_chunk", "lccrf_auto_algo",
-    "lccrf_strerror", "lccrf_version",
+    "lccrf_strerror", "lccrf_version", "lccrf_marginals_static", "lccrf_static_scratch_bytes",
 )
 
 _lib = None
@@ -87,6 +87,10 @@ def load_library() -> ctypes.CDLL:
     lib.lccrf_argmax_structured.argtypes = sbase + [vp, vp, vp, sz, vp]
     for n in ("lccrf_log_partition_structured", "lccrf_marginals_structured", "lccrf_argmax_structured"):
         getattr(lib, n).restype = i
+    lib.lccrf_marginals_static.argtypes = base + [vp, vp, vp]
+    lib.lccrf_marginals_static.restype = i
+    lib.lccrf_static_scratch_bytes.argtypes = []
+    lib.lccrf_static_scratch_bytes.restype = sz
     lib.lccrf_set_scan_chunk.argtypes = [i]
     lib.lccrf_set_scan_chunk.restype = i
     lib.lccrf_auto_algo.argtypes = [i, i, i, i]
@@ -195,6 +199,21 @@ def lccrf_marginals(phi: torch.Tensor, lengths: Optional[torch.Tensor] = None, *
                                       _stream(phi.device), algo)
     _check(rc, "lccrf_marginals")
     return logZ, out
+
+
+def lccrf_marginals_static(phi: torch.Tensor, lengths: Optional[torch.Tensor], out: torch.Tensor,
+                           logZ: torch.Tensor) -> None:
+    """``lccrf_marginals`` into the caller's ``out`` [B, N, T, T] and ``logZ`` [B] (float32, on phi's device)
+    with the library's built-in scratch buffer: nothing is allocated, here or in the library."""
+    lib = load_library()
+    dt, B, N, T = _phi_args(phi)
+    for t, shape in ((out, (B, N, T, T)), (logZ, (B,))):
+        if t.dtype != torch.float32 or tuple(t.shape) != shape or not t.is_contiguous() or t.device != phi.device:
+            raise ValueError(f"outputs must be contiguous float32 tensors of shape {shape} on phi's device")
+    with torch.cuda.device(phi.device):
+        rc = lib.lccrf_marginals_static(phi.data_ptr(), dt, _len_ptr(lengths, B, phi.device), B, N, T,
+                                        logZ.data_ptr(), out.data_ptr(), _stream(phi.device))
+    _check(rc, "lccrf_marginals_static")
 
 
 def lccrf_argmax(phi: torch.Tensor, lengths: Optional[torch.Tensor] = None, *,

@@ -3,7 +3,31 @@
 #include "../../include/lccrf.h"
 #include "lccrf_launch.h"
 
+#include <mutex>
+
+// Built-in scratch of lccrf_marginals_static: device memory inside the library's code object, one
+// copy on every GPU the library is loaded on, held until the process ends.  In host code the name
+// only stands for the symbol; its device address comes from hipGetSymbolAddress (static_scratch()).
+#define LCCRF_STATIC_SCRATCH_BYTES (64u << 20)
+static __device__ __align__(256) unsigned char scratch[LCCRF_STATIC_SCRATCH_BYTES];
+
 namespace {
+
+// Device address of `scratch` on the current device, looked up once per device.
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices] = {};
+void* static_scratch() {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void* p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess) return nullptr;
+        g_scratch_ptr[dev] = p;
+    }
+    return g_scratch_ptr[dev];
+}
 
 constexpr size_t kAlign = 256;
 inline size_t round_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
@@ -288,6 +312,20 @@ int lccrf_marginals(const void* phi, lccrf_dtype dt, const int32_t* lengths, int
                                 LCCRF_ALGO_AUTO);
 }
 
+size_t lccrf_static_scratch_bytes(void) { return LCCRF_STATIC_SCRATCH_BYTES; }
+
+int lccrf_marginals_static(const void* phi, lccrf_dtype dt, const int32_t* lengths, int B, int N, int T, float* logZ,
+                           float* marginals, void* stream) {
+    const size_t need = lccrf_workspace_bytes(LCCRF_OP_MARGINALS, B, N, T, dt);
+    if (need == 0) return LCCRF_EINVAL;
+    if (need > LCCRF_STATIC_SCRATCH_BYTES) return LCCRF_ETOOBIG;
+    if (!phi || !marginals) return LCCRF_ENULL;
+    void* ws = static_scratch();
+    if (!ws) return LCCRF_ELAUNCH;
+    return lccrf_marginals_algo(phi, dt, lengths, B, N, T, logZ, marginals, ws, LCCRF_STATIC_SCRATCH_BYTES, stream,
+                                LCCRF_ALGO_AUTO);
+}
+
 int lccrf_argmax(const void* phi, lccrf_dtype dt, const int32_t* lengths, int B, int N, int T, float* best_score,
                  int32_t* tags, void* workspace, size_t workspace_bytes, void* stream) {
     return lccrf_argmax_algo(phi, dt, lengths, B, N, T, best_score, tags, workspace, workspace_bytes, stream,
@@ -536,6 +574,7 @@ const char* lccrf_strerror(int code) {
         case LCCRF_EALIGN: return "a buffer is misaligned";
         case LCCRF_ELAUNCH: return "the HIP runtime refused a kernel launch";
         case LCCRF_ENOTIMPL: return "the requested schedule is not available for this shape";
+        case LCCRF_ETOOBIG: return "the shape needs more scratch than the library's built-in buffer holds";
         default: return "unknown lccrf status";
     }
 }

@@ -36,7 +36,7 @@ def test_every_declared_symbol_is_exported(lib):
 def test_version_and_strerror(lib):
     assert lib.lccrf_version() >= 100
     assert binding.strerror(0) == "ok"
-    for code in range(-6, 0):
+    for code in range(-7, 0):
         assert "unknown" not in binding.strerror(code)
     assert "unknown" in binding.strerror(-99)
 
