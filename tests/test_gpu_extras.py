@@ -134,15 +134,23 @@ def test_entropy_named_workloads(crf, oracle_mod, key):
     _check_entropy(crf, oracle_mod, workloads.phi_batch(w), workloads.lengths(w), key)
 
 
-def test_entropy_bounds_at_config4_shape(crf):
-    """Full-size config 4 (the oracle's marginals of one such sequence are checked in the sampled test
-    of the marginals): here the property 0 <= H <= L log T on all sequences, and agreement with
-    H = logZ - sum mu phi formed from the library's own marginals on one sequence."""
+def test_entropy_at_config4_full_size(crf, oracle_mod):
+    """Full-size config 4, the whole batch in one call (the launch configuration the benchmark times):
+    0 <= H <= L log T on all sequences, and three full-length sequences against the oracle, which forms
+    H = logZ - sum_e p(e) phi(e) from its own float64 marginals."""
     w = workloads.WORKLOADS["cfg4"]
     phi = torch.empty(w.B, w.N, w.T, w.T, dtype=torch.float32, device="cuda")
     workloads.phi_batch(w, out=phi)
-    H = crf.lccrf_entropy(phi).cpu().numpy()
+    H = crf.lccrf_entropy(phi).cpu().numpy().astype(np.float64)
     assert ((H >= 0) & (H <= w.N * math.log(w.T))).all()
-    lz, mu = crf.lccrf_marginals(phi[:1].contiguous())
-    ref = float(lz[0].double() - (mu[0].double() * phi[0].double()).sum())
-    assert H[0] == pytest.approx(ref, rel=2e-4)
+    pick = [0, 29, 63]
+    want = oracle_mod.entropy(torch.stack([workloads.phi_sequence(w, b) for b in pick]).contiguous(), None)
+    assert np.all(np.abs(H[pick] - want) <= 1e-4 * np.maximum(1.0, np.abs(want))), f"{H[pick]} vs {want}"
+    # the path's log-probability at full size: the best path of every sequence, three of them against the oracle
+    _, best = crf.lccrf_argmax(phi)
+    lp = crf.lccrf_log_prob(phi, best).cpu().numpy().astype(np.float64)
+    phi_pick = torch.stack([workloads.phi_sequence(w, b) for b in pick]).contiguous()
+    want_lp = oracle_mod.log_prob(phi_pick, best[pick].cpu().numpy(), None)
+    want_lz = oracle_mod.log_partition(phi_pick, None)
+    tol = 1e-5 * np.maximum(1.0, np.maximum(np.abs(want_lz), np.abs(want_lp + want_lz)))
+    assert np.all(np.abs(lp[pick] - want_lp) <= tol), f"{lp[pick]} vs {want_lp}"

@@ -107,7 +107,8 @@ def check_case(crf, oracle_mod, phi_cpu, lens_cpu, *, poison=True, algo=0, what=
                     f"{what}: Viterbi path differs in sequence {b} (gap {gap[b]:.3g})"
             elif np.isfinite(want_score[b]):
                 s = _path_score(phi64[b], y, L)
-                assert abs(s - want_score[b]) <= LOGZ_RTOL * max(1.0, abs(want_score[b])) + GAP_MIN
+                # a near-tie: any path whose own score is the best score within the logZ tolerance
+                assert abs(s - want_score[b]) <= LOGZ_RTOL * max(1.0, abs(want_score[b]))
 
 
 # ---------------------------------------------------------------------------------------
@@ -331,34 +332,65 @@ def test_config5_long_peaked_bf16(crf, oracle_mod):
     check_case(crf, oracle_mod, phi, lens, poison=False, what="cfg5")
 
 
-def test_config4_full_size_sampled(crf, oracle_mod):
-    """The 2.1 GB workload in the launch configuration the benchmark times.  The GPU runs the
-    whole batch; the oracle recomputes a sample of sequences (sequences are independent, so
-    each sampled sequence is checked in full), and sum-to-one is checked on all."""
+def test_config4_full_size_all_sequences(crf, oracle_mod):
+    """The 2.1 GB workload in the launch configuration the benchmark times.  The GPU runs the whole
+    batch in one call per query; the oracle then recomputes ALL 64 sequences, eight at a time (to bound
+    host memory: the float64 marginals of eight sequences are 0.5 GB), and every logZ, every marginal,
+    every Viterbi score and every tag path is compared."""
     w = workloads.WORKLOADS["cfg4"]
     dev = torch.device("cuda:0")
     phi_dev = torch.empty(w.B, w.N, w.T, w.T, dtype=torch.float32, device=dev)
     workloads.phi_batch(w, out=phi_dev)
     lens = workloads.lengths(w)
     lens_dev = lens.to(dev)
-    lz, mu = crf.lccrf_marginals(phi_dev, lens_dev)
+    mu = torch.full((w.B, w.N, w.T, w.T), float("nan"), device=dev)
+    lz = torch.full((w.B,), float("nan"), device=dev)
+    crf.lccrf_marginals(phi_dev, lens_dev, out=mu, logZ=lz)
     lz_only = crf.lccrf_log_partition(phi_dev, lens_dev)
     score, tags = crf.lccrf_argmax(phi_dev, lens_dev)
     torch.cuda.synchronize()
-    sums = mu.sum(dim=(2, 3)).cpu().numpy()
-    assert np.abs(sums - 1.0).max() < 1e-4
-    assert np.isfinite(lz.cpu().numpy()).all()
     assert torch.allclose(lz, lz_only, rtol=1e-6, atol=0)
-    for b in (0, 29, 63):
-        phi_b = workloads.phi_sequence(w, b).unsqueeze(0)
-        want_lz, want_mu = oracle_mod.marginals(phi_b, None)
-        _close_logz(lz[b:b + 1].cpu().numpy(), want_lz, f"cfg4 seq {b}")
-        err = np.abs(mu[b].cpu().numpy() - want_mu[0]).max()
-        assert err <= 1e-5, f"cfg4 seq {b}: max |mu - oracle| = {err:.3e}"
-        want_score, want_tags, gap = oracle_mod.viterbi(phi_b, None)
-        _close_logz(score[b:b + 1].cpu().numpy(), want_score, f"cfg4 seq {b} score")
-        if gap[0] > GAP_MIN:
-            assert np.array_equal(tags[b].cpu().numpy(), want_tags[0])
+    got_lz = lz.cpu().numpy()
+    got_lz_only = lz_only.cpu().numpy()
+    got_score = score.cpu().numpy()
+    got_tags = tags.cpu().numpy()
+    worst = 0.0
+    graded_paths = 0
+    for b0 in range(0, w.B, 8):
+        pick = list(range(b0, min(b0 + 8, w.B)))
+        phi_b = torch.stack([workloads.phi_sequence(w, b) for b in pick]).contiguous()
+        want_lz, want_mu = oracle_mod.marginals(phi_b, lens[pick].numpy())
+        _close_logz(got_lz[pick], want_lz, f"cfg4 seqs {b0}.. marginals.logZ")
+        _close_logz(got_lz_only[pick], want_lz, f"cfg4 seqs {b0}.. log_partition")
+        got_mu = mu[b0:b0 + len(pick)].cpu().numpy()
+        assert np.isfinite(got_mu).all()
+        err = float(np.abs(got_mu - want_mu).max())
+        worst = max(worst, err)
+        assert err <= 1e-5, f"cfg4 seqs {b0}..{pick[-1]}: max |mu - oracle| = {err:.3e}"
+        assert not got_mu[:, 0, 1:].any(), "rows s > 0 of position 0 must be exact zeros"
+        del got_mu, want_mu
+        want_score, want_tags, gap = oracle_mod.viterbi(phi_b, lens[pick].numpy())
+        _close_logz(got_score[pick], want_score, f"cfg4 seqs {b0}.. argmax.score")
+        phi64 = phi_b.numpy()
+        for k, b in enumerate(pick):
+            y = got_tags[b]
+            assert ((y >= 0) & (y < w.T)).all()
+            if gap[k] > GAP_MIN:
+                assert np.array_equal(y, want_tags[k]), f"cfg4 seq {b}: Viterbi path differs (gap {gap[k]:.3g})"
+                graded_paths += 1
+            else:   # a near-tie: any path whose own score is the best score within the logZ tolerance
+                s = _path_score(phi64[k].astype(np.float64), y, w.N)
+                assert abs(s - want_score[k]) <= LOGZ_RTOL * max(1.0, abs(want_score[k]))
+    assert graded_paths >= w.B // 2, "too few sequences with a clear top-2 gap to grade the paths"
+    print(f"cfg4: all {w.B} sequences, max |mu - oracle| = {worst:.2e}, {graded_paths} paths graded bit-exact")
+
+
+def test_paired_second_pass_bf16_full_length(crf, oracle_mod):
+    """T = 128, N = 512 (config 4's chain length) with bfloat16-stored potentials: two workgroups per
+    chain exchange half vectors 256 times in each direction; every marginal against the oracle."""
+    phi, _ = workloads.random_case(4500, 3, 512, 128, scale=3.0, dtype="bf16")
+    lens = torch.tensor([512, 511, 300], dtype=torch.int32)
+    check_case(crf, oracle_mod, phi, lens, poison=False, what="paired bf16 N=512", queries=("logz", "mu"))
 
 
 def test_paper_benchmark_shape(crf, oracle_mod):

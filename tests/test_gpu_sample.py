@@ -59,6 +59,33 @@ def test_sample_bf16_and_forbidden_edges(crf, oracle_mod):
     assert (got[2] == 0).all() and (got[1, 10] != 5)
 
 
+def _draws_miss(oracle_mod, phi_b, L, y, u_b, what):
+    """How far (relative to the total weight) the worst draw of the path y [L] of ONE sequence lies outside the
+    interval of its tag, given the path's own tag above it, with the oracle's fp64 alpha.  phi_b: [N, T, T] CPU
+    tensor, u_b: [N] float64."""
+    N, T, _ = phi_b.shape
+    if L == 0:
+        return 0.0
+    alpha, _, _ = oracle_mod.forward_backward(phi_b.unsqueeze(0).contiguous(), np.array([L], dtype=np.int32))
+    phi32 = phi_b.to(torch.float32).numpy()
+    y = y[:L].astype(np.int64)
+    assert ((y >= 0) & (y < T)).all()
+    logw = alpha[0, :L].copy()                                       # [L, T] over the candidate tag s
+    logw[:L - 1] += phi32[np.arange(1, L), :, y[1:]].astype(np.float64)   # + phi_{i+1}(s, y_{i+1})
+    w = np.exp(logw - logw.max(axis=1, keepdims=True))
+    cum = np.cumsum(w, axis=1)
+    tot = cum[:, -1]
+    target = u_b[:L] * tot
+    upper = cum[np.arange(L), y]
+    lower = upper - w[np.arange(L), y]
+    assert (w[np.arange(L), y] > 0).all(), f"{what}: a tag of weight 0 was drawn"
+    below = np.maximum(lower - target, 0.0) / tot                    # the draw lies below the tag's interval
+    # above the interval is allowed only for the last tag of positive weight (the rounding rule)
+    is_last = np.array([y[i] == np.nonzero(w[i] > 0)[0][-1] for i in range(L)])
+    above = np.where(is_last, 0.0, np.maximum(target - upper, 0.0) / tot)
+    return max(float(below.max()), float(above.max()))
+
+
 def _check_every_draw(crf, oracle_mod, phi, lens, seed, what, tol=1e-4):
     """Long chains: the oracle's closest draw is almost surely within rounding of a boundary somewhere
     along thousands of positions, after which the two chains condition on different tags.  So every
@@ -68,32 +95,28 @@ def _check_every_draw(crf, oracle_mod, phi, lens, seed, what, tol=1e-4):
     u = torch.rand(B, N, generator=torch.Generator().manual_seed(seed))
     got = crf.lccrf_sample(phi.cuda(), u.cuda(), None if lens is None else lens.cuda()).cpu().numpy()
     lens_np = np.full((B,), N) if lens is None else np.clip(lens.numpy(), 0, N)
-    alpha, _, _ = oracle_mod.forward_backward(phi, lens_np.astype(np.int32))
-    phi64 = phi.to(torch.float32).numpy()
     un = u.numpy().astype(np.float64)
     worst = 0.0
     for b in range(B):
         L = int(lens_np[b])
         assert (got[b, L:] == -1).all(), f"{what}: tags past the length of sequence {b}"
-        if L == 0:
-            continue
-        y = got[b, :L].astype(np.int64)
-        assert ((y >= 0) & (y < T)).all()
-        logw = alpha[b, :L].copy()                                   # [L, T] over the candidate tag s
-        logw[:L - 1] += phi64[b, np.arange(1, L), :, y[1:]].astype(np.float64)   # + phi_{i+1}(s, y_{i+1})
-        w = np.exp(logw - logw.max(axis=1, keepdims=True))
-        cum = np.cumsum(w, axis=1)
-        tot = cum[:, -1]
-        target = un[b, :L] * tot
-        upper = cum[np.arange(L), y]
-        lower = upper - w[np.arange(L), y]
-        assert (w[np.arange(L), y] > 0).all(), f"{what}: a tag of weight 0 was drawn in sequence {b}"
-        below = np.maximum(lower - target, 0.0) / tot                # the draw lies below the tag's interval
-        # above the interval is allowed only for the last tag of positive weight (the rounding rule)
-        is_last = np.array([y[i] == np.nonzero(w[i] > 0)[0][-1] for i in range(L)])
-        above = np.where(is_last, 0.0, np.maximum(target - upper, 0.0) / tot)
-        worst = max(worst, float(below.max()), float(above.max()))
+        worst = max(worst, _draws_miss(oracle_mod, phi[b], L, got[b], un[b], f"{what} sequence {b}"))
     assert worst <= tol, f"{what}: a draw misses its tag's interval by {worst:.2e} of the total weight"
+
+
+def test_sample_config4_full_size(crf, oracle_mod):
+    """Full-size config 4, the whole batch in one call: every tag in range on all sequences, and every draw of
+    three full-length sequences against the oracle's fp64 interval of its tag."""
+    w = workloads.WORKLOADS["cfg4"]
+    phi = torch.empty(w.B, w.N, w.T, w.T, dtype=torch.float32, device="cuda")
+    workloads.phi_batch(w, out=phi)
+    u = torch.rand(w.B, w.N, generator=torch.Generator().manual_seed(44))
+    got = crf.lccrf_sample(phi, u.cuda()).cpu().numpy()
+    assert ((got >= 0) & (got < w.T)).all()
+    un = u.numpy().astype(np.float64)
+    for b in (1, 30, 63):
+        miss = _draws_miss(oracle_mod, workloads.phi_sequence(w, b), w.N, got[b], un[b], f"cfg4 sequence {b}")
+        assert miss <= 1e-4, f"cfg4 sequence {b}: a draw misses its tag's interval by {miss:.2e} of the total weight"
 
 
 @pytest.mark.parametrize("T,N", [(3, 6000), (5, 700), (16, 3000), (20, 300), (32, 600), (48, 400), (128, 200)])
