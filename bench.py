@@ -2,11 +2,13 @@
 """Benchmark of the linear-chain CRF hot path on one MI355X.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg4] [--no-cpu-baseline]
+                    [--no-per-config] [--no-other-queries] [--cold] [--ceilings]
 
 One "step" is one `lccrf_marginals` call over the whole synthetic batch: both log-semiring
 chains, logZ, and the fused write of every edge marginal.  Inputs are resident in HBM before
 the timed region starts.  The headline number is potentials per second, B*N*T*T / time per
-step.  Prints exactly one JSON line on stdout; everything else goes to stderr.
+step, on the headline workload (cfg4).  Prints exactly one JSON line on stdout; everything else
+goes to stderr.
 
 Extra objects in the line:
   roofline      for the dominant kernel (the second pass, which re-reads phi and writes the
@@ -14,6 +16,16 @@ Extra objects in the line:
                 between its passes: algorithmic bytes = (sizeof(phi element) + 4) per potential.
   cpu_baseline  the CPU oracle (as it stands, OpenMP over the batch) timed on this host on a
                 bounded sample of the same workload.
+  per_config    every other synthetic workload (cfg1, cfg2, cfg3, cfg5 and the paper's own benchmark
+                shape) and the headline one: marginals, log-partition and argmax timed call by call
+                with HIP events (median and minimum), with warm caches and, for working sets below the
+                256 MB memory-side cache, cold (a 512 MB scratch buffer is rewritten before every
+                call); algorithmic bytes over the positions inside the chains, the fraction of the HBM
+                peak they amount to, the bound that applies, and the parity of the same buffers
+                against the oracle (max |mu - oracle|, relative logZ error, Viterbi paths).
+  stream_ceilings  what 128 / 256 / 1024 workgroups of this chip read, and read + write, streaming
+                contiguous regions (the library's instrumentation probe): the practical ceilings
+                beside the datasheet peak.
   other_queries log-partition alone, Viterbi decode, entropy, the log-probability of a path, one sample, and the
                 cross-entropy and KL divergence against a second chain, the semi-Markov log-partition over the same bytes,
                 timed the same way (context).
@@ -30,6 +42,8 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0  # MI355X datasheet HBM3E bandwidth
+CACHE_BYTES = 256 << 20  # memory-side cache: smaller working sets are also timed cold
+PER_CONFIG = ("cfg1", "cfg2", "cfg3", "cfg5", "paper_lccrf")
 
 
 def log(*a):
@@ -41,9 +55,10 @@ def median(xs):
     return xs[len(xs) // 2]
 
 
-def stored_traffic(workload: str):
+def committed_traffic(workload: str):
     """HBM bytes per launch of the dominant kernel from the committed rocprofv3 --pmc summary
-    (profiles/marginals_<workload>_traffic.txt, line `traffic_bytes_per_launch: N`), else None."""
+    (profiles/marginals_<workload>_traffic.txt, line `traffic_bytes_per_launch: N`), else None.
+    Counters cannot be read from inside the run; the summary names the command that made it."""
     path = os.path.join(ROOT, "profiles", f"marginals_{workload}_traffic.txt")
     try:
         with open(path) as f:
@@ -57,8 +72,8 @@ def stored_traffic(workload: str):
 
 def cpu_baseline(w, budget_s: float = 20.0):
     """Time the oracle's marginals on a bounded sample of the workload (whole sequences)."""
-    import numpy as np
     import oracle
+    import torch
     from paper_2308_03291_amd import workloads
     threads = oracle.threads()
     lens = workloads.lengths(w)
@@ -71,7 +86,6 @@ def cpu_baseline(w, budget_s: float = 20.0):
     per_pot = (time.perf_counter() - t0) / (probe_pos * w.T * w.T)
     per_seq = per_pot * w.N * w.T * w.T
     nseq = int(max(1, min(w.B, budget_s * threads / max(per_seq, 1e-9) / 2)))
-    import torch
     phi = torch.stack([workloads.phi_sequence(w, b, trans) for b in range(nseq)]).contiguous()
     sample_lens = lens[:nseq].numpy()
     cores = int(min(threads, nseq))
@@ -88,6 +102,139 @@ def cpu_baseline(w, budget_s: float = 20.0):
                       f"({pots} potentials a pass, {reps} passes, {dt:.2f} s wall, OpenMP over sequences)"}
 
 
+class Timer:
+    """Times single calls with a pair of HIP events on the current stream."""
+
+    def __init__(self, torch, scratch):
+        self.torch, self.scratch = torch, scratch
+
+    def events(self, n):
+        evs = [self.torch.cuda.Event(enable_timing=True) for _ in range(n)]
+        for e in evs:
+            e.record()   # materialise the HIP handles
+        self.torch.cuda.synchronize()
+        return evs
+
+    def evict(self):
+        self.scratch.add_(1)   # rewrites 512 MB: nothing of the workload stays in L2 or the memory-side cache
+
+    def run(self, fn, calls, cold):
+        for _ in range(2):
+            fn()
+        evs = self.events(2 * calls)
+        for k in range(0, len(evs), 2):
+            if cold:
+                self.evict()
+            evs[k].record()
+            fn()
+            evs[k + 1].record()
+        self.torch.cuda.synchronize()
+        ts = [evs[k].elapsed_time(evs[k + 1]) * 1e3 for k in range(0, len(evs), 2)]
+        return {"median_us": median(ts), "min_us": min(ts), "calls": calls}
+
+
+def parity(crf, oracle, phi_cpu, lens_cpu, lz, mu, score, tags, pick):
+    """The GPU results of sequences `pick` against the oracle on the same inputs."""
+    import numpy as np
+    sub = phi_cpu[pick].contiguous()
+    ln = lens_cpu[pick].numpy()
+    want_lz, want_mu = oracle.marginals(sub, ln)
+    want_score, want_tags, gap = oracle.viterbi(sub, ln)
+    got_lz = lz[pick].cpu().numpy().astype(np.float64)
+    mu_err = float(np.abs(mu[pick].cpu().numpy() - want_mu).max())
+    lz_err = float((np.abs(got_lz - want_lz) / np.maximum(1.0, np.abs(want_lz))).max())
+    sc_err = float((np.abs(score[pick].cpu().numpy() - want_score) / np.maximum(1.0, np.abs(want_score))).max())
+    got_tags = tags[pick].cpu().numpy()
+    clear = gap > 1e-3
+    same = [bool(np.array_equal(got_tags[k], want_tags[k])) for k in range(len(pick))]
+    return {"sequences_checked": len(pick), "max_abs_marginal_error": mu_err, "max_rel_logz_error": lz_err,
+            "max_rel_score_error": sc_err, "paths_with_clear_gap": int(clear.sum()),
+            "paths_identical_where_gap_clear": int(sum(s for s, c in zip(same, clear) if c))}
+
+
+def bound_of(w, algo_scan, longest):
+    """The ceiling that applies to a workload, as its measurements show (profiles/ holds the counters)."""
+    bytes_marg = w.B * w.N * w.T * w.T * ((2 if w.dtype == "bf16" else 4) * 2 + 4)
+    if w.key == "cfg4":
+        return "hbm"
+    if bytes_marg < (32 << 20):
+        return "latency: launches plus the serial depth of the chains; the batch is far too small to load the chip"
+    return ("latency: serial depth of " + ("the scan's three phases" if algo_scan else f"{longest // 2} dependent steps per half chain")
+            + " at about one wave per SIMD; HBM fraction reported for scale")
+
+
+def bench_config(crf, workloads, oracle, torch, timer, key, calls, dev, with_parity=True):
+    w = workloads.WORKLOADS[key]
+    esz = 2 if w.dtype == "bf16" else 4
+    phi_cpu = workloads.phi_batch(w)
+    lens_cpu = workloads.lengths(w)
+    phi, lens = phi_cpu.to(dev), lens_cpu.to(dev)
+    dtc = crf.LCCRF_BF16 if esz == 2 else crf.LCCRF_F32
+    mu = torch.empty(w.B, w.N, w.T, w.T, dtype=torch.float32, device=dev)
+    lz = torch.empty(w.B, dtype=torch.float32, device=dev)
+    lz1 = torch.empty(w.B, dtype=torch.float32, device=dev)
+    tags = torch.empty(w.B, w.N, dtype=torch.int32, device=dev)
+    score = torch.empty(w.B, dtype=torch.float32, device=dev)
+    ws = torch.empty(max(crf.workspace_bytes(op, w.B, w.N, w.T, dtc) for op in (0, 1, 2)), dtype=torch.uint8, device=dev)
+    pots = w.B * w.N * w.T * w.T
+    eff_pos = int(lens_cpu.clamp(0, w.N).sum().item())
+    eff_pots = eff_pos * w.T * w.T
+    working_set = pots * (esz + 4)
+    queries = {
+        "marginals": (lambda: crf.lccrf_marginals(phi, lens, out=mu, logZ=lz, workspace=ws), 2 * esz + 4, crf.OP_MARGINALS),
+        "log_partition": (lambda: crf.lccrf_log_partition(phi, lens, out=lz1, workspace=ws), esz, crf.OP_LOGZ),
+        "argmax": (lambda: crf.lccrf_argmax(phi, lens, out=tags, score=score, workspace=ws), esz, crf.OP_ARGMAX),
+    }
+    out = {"shape": {"B": w.B, "N": w.N, "T": w.T, "dtype": w.dtype}, "potentials": pots,
+           "effective_potentials": eff_pots, "working_set_bytes": working_set, "queries": {}}
+    scan_any = False
+    for name, (fn, bpp, op) in queries.items():
+        scan = crf.auto_algo(op, w.B, w.N, w.T) == crf.ALGO_SCAN
+        scan_any = scan_any or (scan and name == "marginals")
+        q = {"schedule": "scan" if scan else "sequential", "algorithmic_bytes": eff_pots * bpp,
+             "warm": timer.run(fn, calls, cold=False)}
+        states = ["warm"]
+        if working_set < CACHE_BYTES:
+            q["cold"] = timer.run(fn, calls, cold=True)
+            states.append("cold")
+        for st in states:
+            t = q[st]["median_us"] * 1e-6
+            q[st]["potentials_per_s"] = pots / t
+            q[st]["effective_potentials_per_s"] = eff_pots / t
+            q[st]["hbm_frac"] = eff_pots * bpp / t / 1e9 / HBM_PEAK_GBPS
+        out["queries"][name] = q
+    out["bound"] = bound_of(w, scan_any, int(lens_cpu.max().item()))
+    m = out["queries"]["marginals"]
+    log(f"[bench] {key}: marginals {m['warm']['median_us']:.1f} us warm"
+        + (f" / {m['cold']['median_us']:.1f} us cold ({100 * m['cold']['hbm_frac']:.1f} % of HBM peak)" if "cold" in m else "")
+        + f", logZ {out['queries']['log_partition']['warm']['median_us']:.1f}, argmax {out['queries']['argmax']['warm']['median_us']:.1f}")
+    if with_parity:
+        torch.cuda.synchronize()
+        out["parity"] = parity(crf, oracle, phi_cpu, lens_cpu, lz, mu, score, tags, list(range(w.B)))
+    return out
+
+
+def stream_ceilings(crf, torch, src, dst, timer_events):
+    """What G workgroups stream (read only; read + write), GB/s, best of 5."""
+    sink = torch.zeros(1, dtype=torch.float32, device=src.device)
+    out = {}
+    for G in (64, 128, 256, 512, 1024, 4096):
+        for mode, d in (("read", None), ("read_write", dst)):
+            best = None
+            for _ in range(6):
+                a, b = timer_events(2)
+                a.record()
+                nbytes = crf.lccrf_stream_probe(src, d, G, sink)
+                b.record()
+                torch.cuda.synchronize()
+                ms = a.elapsed_time(b)
+                best = ms if best is None else min(best, ms)
+            moved = nbytes * (2 if d is not None else 1)
+            out[f"{mode}_{G}wg"] = {"GB_per_s": moved / (best * 1e-3) / 1e9, "ms": best, "bytes": moved}
+            log(f"[bench] stream probe {mode:10s} {G:5d} workgroups: {moved / (best * 1e-3) / 1e9:7.1f} GB/s")
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -96,6 +243,8 @@ def main():
     ap.add_argument("--workload", default="cfg4")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-other-queries", action="store_true")
+    ap.add_argument("--no-per-config", action="store_true")
+    ap.add_argument("--calls", type=int, default=30, help="timed calls per query and cache state in per_config")
     ap.add_argument("--cold", action="store_true",
                     help="write a 512 MB scratch buffer before every timed call, so that nothing of the "
                          "workload is left in L2 or the 256 MB memory-side cache (matters for workloads "
@@ -104,6 +253,8 @@ def main():
                     help="also run one plain elementwise kernel of known size (reads and writes exactly "
                          "4 bytes per potential) so that rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE "
                          "readings can be scaled to bytes")
+    ap.add_argument("--ceilings", action="store_true",
+                    help="only run the streaming probe (what G workgroups read and write) and print its table")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU (sequences are independent; sharding the batch over "
@@ -116,6 +267,21 @@ def main():
         sys.exit("bench.py: no GPU visible")
     crf.load_library()
     dev = torch.device("cuda:0")
+
+    def new_events(n):
+        evs = [torch.cuda.Event(enable_timing=True) for _ in range(n)]
+        for e in evs:
+            e.record()   # materialise the HIP handles
+        torch.cuda.synchronize()
+        return evs
+
+    if args.ceilings:
+        src = torch.zeros(1 << 29, dtype=torch.float32, device=dev)   # 2 GiB each
+        dst = torch.empty_like(src)
+        print(json.dumps({"stream_ceilings": stream_ceilings(crf, torch, src, dst, new_events),
+                          "hbm_peak_GB_per_s": HBM_PEAK_GBPS}), flush=True)
+        return
+
     w = workloads.WORKLOADS[args.workload]
     esz = 2 if w.dtype == "bf16" else 4
     dt = torch.bfloat16 if w.dtype == "bf16" else torch.float32
@@ -137,17 +303,11 @@ def main():
     torch.cuda.synchronize()
     log(f"[bench] inputs resident after {time.perf_counter() - t0:.1f} s")
 
-    def new_events(n):
-        evs = [torch.cuda.Event(enable_timing=True) for _ in range(n)]
-        for e in evs:
-            e.record()   # materialise the HIP handles
-        torch.cuda.synchronize()
-        return evs
-
-    scratch = torch.empty(512 << 20, dtype=torch.uint8, device=dev) if args.cold else None
+    scratch = torch.empty(512 << 20, dtype=torch.uint8, device=dev)
+    timer = Timer(torch, scratch)
 
     def evict():
-        if scratch is not None:
+        if args.cold:
             scratch.add_(1)
 
     def run_step(evs=None):
@@ -195,8 +355,13 @@ def main():
     achieved = alg_bytes / (pass2_avg * 1e-3) / 1e9
     roofline = {"bound": "hbm", "kernel": kernel,
                 "achieved": achieved, "peak": HBM_PEAK_GBPS,
-                "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS, "traffic": stored_traffic(w.key),
+                "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS,
+                # counters cannot be read inside the run: this figure comes from the committed rocprofv3 --pmc summary
+                "traffic": committed_traffic(w.key), "traffic_source": f"profiles/marginals_{w.key}_traffic.txt (committed)",
                 "algorithmic_bytes_per_launch": alg_bytes, "avg_launch_ms": pass2_avg,
+                "first_pass": {"kernel": "chain_half_kernel", "algorithmic_bytes": eff_pots * esz,
+                               "avg_ms": sum(pass1) / len(pass1),
+                               "frac": eff_pots * esz / (sum(pass1) / len(pass1) * 1e-3) / 1e9 / HBM_PEAK_GBPS},
                 "whole_call": {"algorithmic_bytes": call_bytes, "avg_ms": sum(whole) / len(whole),
                                "achieved": call_bytes / (sum(whole) / len(whole) * 1e-3) / 1e9,
                                "frac": call_bytes / (sum(whole) / len(whole) * 1e-3) / 1e9 / HBM_PEAK_GBPS}}
@@ -207,6 +372,41 @@ def main():
         torch.cuda.synchronize()
         log(f"[bench] calibration kernel: elementwise add over {pots} floats "
             f"({pots * 4} bytes read, {pots * 4} bytes written)")
+
+    per_config = None
+    ceilings = None
+    if not args.no_per_config:
+        import oracle
+        # the headline workload: the three main queries call by call, and parity of these very buffers on 8 sequences
+        crf.lccrf_marginals(phi, lens, out=mu, logZ=lz, workspace=ws)
+        crf.lccrf_argmax(phi, lens, out=tags, score=score, workspace=ws)
+        torch.cuda.synchronize()
+        head = {"shape": {"B": w.B, "N": w.N, "T": w.T, "dtype": w.dtype}, "potentials": pots,
+                "effective_potentials": eff_pots, "working_set_bytes": pots * (esz + 4), "queries": {}, "bound": "hbm"}
+        pick = list(range(0, w.B, max(1, w.B // 8)))[:8]
+        sub = torch.stack([workloads.phi_sequence(w, b, workloads.shared_transitions(w)) for b in pick])
+        head["parity"] = parity(crf, oracle, sub, lens_cpu[pick], lz[pick], mu[pick], score[pick], tags[pick],
+                                list(range(len(pick))))
+        del sub
+        lz1 = torch.empty_like(lz)
+        for name, fn, bpp in (
+                ("marginals", lambda: crf.lccrf_marginals(phi, lens, out=mu, logZ=lz, workspace=ws), 2 * esz + 4),
+                ("log_partition", lambda: crf.lccrf_log_partition(phi, lens, out=lz1, workspace=ws), esz),
+                ("argmax", lambda: crf.lccrf_argmax(phi, lens, out=tags, score=score, workspace=ws), esz)):
+            state = "warm" if pots * (esz + 4) < CACHE_BYTES else "cold"   # larger than the cache: every call is cold
+            q = {"schedule": "sequential", "algorithmic_bytes": eff_pots * bpp, state: timer.run(fn, args.calls, cold=False)}
+            t = q[state]["median_us"] * 1e-6
+            q[state].update(potentials_per_s=pots / t, effective_potentials_per_s=eff_pots / t,
+                            hbm_frac=eff_pots * bpp / t / 1e9 / HBM_PEAK_GBPS)
+            head["queries"][name] = q
+        per_config = {w.key: head}
+        log(f"[bench] {w.key}: parity on {len(pick)} sequences: max |mu - oracle| = {head['parity']['max_abs_marginal_error']:.2e}")
+        # the stream probe on the headline buffers (2 GiB read, 2 GiB written)
+        if esz == 4 and pots * 4 >= (1 << 30):
+            ceilings = stream_ceilings(crf, torch, phi, mu, new_events)
+        for key in PER_CONFIG:
+            if key != w.key:
+                per_config[key] = bench_config(crf, workloads, oracle, torch, timer, key, args.calls, dev)
 
     other = None
     if not args.no_other_queries:
@@ -267,6 +467,10 @@ def main():
                    "effective_potentials": eff_pots},
         "roofline": roofline, "cpu_baseline": base,
     }
+    if per_config is not None:
+        out["per_config"] = per_config
+    if ceilings is not None:
+        out["stream_ceilings"] = ceilings
     if other is not None:
         out["other_queries"] = other
     print(json.dumps(out), flush=True)

@@ -31,10 +31,25 @@
  *    256-byte aligned, not shared by calls that may overlap in time.  Contents on
  *    entry are irrelevant; contents on exit are unspecified.
  *  - 1 <= T <= LCCRF_MAX_T, B >= 1, N >= 1, B*N*T*T < 2^62.
- *  - Return value: LCCRF_OK (0) or a negative lccrf_status.  When an error is
- *    returned nothing has been enqueued.
- *  - Thread safety: entry points keep no mutable global state; concurrent calls
- *    with distinct workspaces are safe.
+ *  - Return value: LCCRF_OK (0) or a negative lccrf_status.  Argument errors (every
+ *    status but LCCRF_ELAUNCH) are found before anything is enqueued.  A query is
+ *    several kernel launches; LCCRF_ELAUNCH means the HIP runtime refused one of
+ *    them, and the launches before it are already enqueued: the outputs and the
+ *    workspace are then unspecified, nothing else is harmed.
+ *  - Thread safety: concurrent calls with distinct workspaces are safe.  The only
+ *    mutable state in the library are two process-wide tuning knobs
+ *    (lccrf_set_scan_chunk, lccrf_set_pair_poll_limit; atomic integers, meant to be
+ *    set once at start-up) and caches of per-device constants.  A call reads the
+ *    knobs once, at its start, so every call is consistent in itself; a workspace
+ *    sized under one chunk setting and used under another is refused with
+ *    LCCRF_EWORKSPACE if it is too small.
+ *  - Repeat runs: results are bit-identical from run to run, with one exception:
+ *    marginals at T = 128 in batches that fill at most a quarter of the chip's
+ *    compute units are computed by pairs of workgroups (see
+ *    lccrf_set_pair_poll_limit); a pair that gives its sequence up hands it to the
+ *    one-workgroup kernel, which rounds differently, so where that hand-over depends
+ *    on timing two runs may differ in the low-order bits (far inside the tolerance).
+ *    LCCRF_ALGO_SEQUENTIAL never uses pairs.
  */
 #ifndef LCCRF_H
 #define LCCRF_H
@@ -122,9 +137,12 @@ int lccrf_marginals(const void* phi, lccrf_dtype dt, const int32_t* lengths,
  * score with respect to the potentials marks):
  *     tags[b][i] in [0, T) for i < lengths[b], -1 for i >= lengths[b]; int32 [B][N].
  *     best_score[b] = score_b(tags[b]); float [B] or NULL.
- * Scores are accumulated in double precision.  Among exactly tied paths the one
- * returned takes the smallest previous tag at every step back from the smallest best
- * final tag.
+ * Scores are accumulated in double precision.  Among exactly tied best paths the one
+ * returned depends on the schedule.  The sequential schedule runs two chains that meet
+ * at position h = lengths[b] / 2 and returns, of all best paths, the one with the
+ * smallest tag at h, then the smallest tag at h-1, h-2, ..., 0 in that order (smallest
+ * predecessor at every step down) and, independently, the smallest tag at h+1, ...,
+ * L-1 (smallest successor at every step up).  The chunked scan returns some best path.
  */
 int lccrf_argmax(const void* phi, lccrf_dtype dt, const int32_t* lengths,
                  int B, int N, int T,
@@ -161,19 +179,6 @@ int lccrf_marginals_algo(const void* phi, lccrf_dtype dt, const int32_t* lengths
 int lccrf_argmax_algo(const void* phi, lccrf_dtype dt, const int32_t* lengths,
                       int B, int N, int T, float* best_score, int32_t* tags,
                       void* workspace, size_t workspace_bytes, void* stream, lccrf_algo algo);
-
-/*
- * Instrumentation for benchmarks (not a query of its own): lccrf_marginals_algo with three
- * caller-created hipEvent_t handles (passed as void*, any may be NULL) recorded on `stream`
- * before the first kernel, between the two passes of the sequential schedule (after every
- * matrix has been read once and the half-way vectors are stored; before the pass that
- * re-reads phi and writes the marginals), and after the last kernel.  Lets a caller time the
- * passes separately with hipEventElapsedTime.  Same results and errors as lccrf_marginals_algo.
- */
-int lccrf_marginals_timed(const void* phi, lccrf_dtype dt, const int32_t* lengths,
-                          int B, int N, int T, float* logZ, float* marginals,
-                          void* workspace, size_t workspace_bytes, void* stream, lccrf_algo algo,
-                          void* ev_begin, void* ev_between, void* ev_end);
 
 /*
  * log p(y) = score(y) - logZ of one given tag path per sequence (paper, section "Structured
@@ -277,9 +282,19 @@ int lccrf_argmax_structured(const float* emit, const float* trans, const int32_t
 /* Positions per chunk of LCCRF_ALGO_SCAN: a process-wide tuning knob.  0 (the default) lets every
  * call choose by its shape (8, 16 or 32: the shortest chunks that the chip still holds all at
  * once); other values outside [4, 4096] return LCCRF_EINVAL and change nothing.  It enters
- * lccrf_workspace_bytes, so set it before sizing a workspace, and not while another thread is
- * inside a query.  Results do not depend on it beyond rounding. */
+ * lccrf_workspace_bytes, so set it before sizing a workspace.  Every call reads it once at its start.
+ * Results do not depend on it beyond rounding. */
 int lccrf_set_scan_chunk(int chunk);
+
+/* How many times a workgroup of the paired second pass of lccrf_marginals (T = 128, batches of at
+ * most a quarter as many sequences as the chip has compute units: two workgroups per chain that swap
+ * half vectors through device memory at every position) looks for its partner's words before it
+ * gives the sequence up; the one-workgroup kernel then recomputes that sequence, so results never
+ * depend on the limit beyond rounding.  A process-wide tuning knob.  Default 32768 polls (some tens
+ * of milliseconds at worst; an exchange between resident partners takes under a microsecond), -1
+ * restores it, 0 gives up without looking (every sequence then takes the one-workgroup kernel: for
+ * tests of that path), more than 2^24 returns LCCRF_EINVAL. */
+int lccrf_set_pair_poll_limit(int polls);
 
 /* The schedule LCCRF_ALGO_AUTO takes for `op` at this shape under the current chunk size:
  * LCCRF_ALGO_SEQUENTIAL or LCCRF_ALGO_SCAN.  Host-side arithmetic, nothing is launched;

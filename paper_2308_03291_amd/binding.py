@@ -34,6 +34,7 @@ EXPORTS = (
     "lccrf_sample", "lccrf_semi_markov_log_partition", "lccrf_log_partition_structured",
     "lccrf_marginals_structured", "lccrf_argmax_structured", "lccrf_set_scan_chunk", "lccrf_auto_algo",
     "lccrf_strerror", "lccrf_version", "lccrf_marginals_static", "lccrf_static_scratch_bytes",
+    "lccrf_set_pair_poll_limit", "lccrf_stream_probe", "lccrf_stream_probe_bytes",
 )
 
 _lib = None
@@ -93,6 +94,12 @@ def load_library() -> ctypes.CDLL:
     lib.lccrf_static_scratch_bytes.restype = sz
     lib.lccrf_set_scan_chunk.argtypes = [i]
     lib.lccrf_set_scan_chunk.restype = i
+    lib.lccrf_stream_probe.argtypes = [vp, vp, sz, i, vp, vp]
+    lib.lccrf_stream_probe.restype = i
+    lib.lccrf_stream_probe_bytes.argtypes = [sz, i]
+    lib.lccrf_stream_probe_bytes.restype = sz
+    lib.lccrf_set_pair_poll_limit.argtypes = [i]
+    lib.lccrf_set_pair_poll_limit.restype = i
     lib.lccrf_auto_algo.argtypes = [i, i, i, i]
     lib.lccrf_auto_algo.restype = i
     _lib = lib
@@ -106,6 +113,12 @@ def strerror(code: int) -> str:
 def set_scan_chunk(chunk: int) -> None:
     """Positions per chunk of ALGO_SCAN (0: default).  Size workspaces after calling this."""
     _check(load_library().lccrf_set_scan_chunk(int(chunk)), "lccrf_set_scan_chunk")
+
+
+def set_pair_poll_limit(polls: int) -> None:
+    """Looks a paired workgroup takes for its partner's words before it gives its sequence up (-1: default,
+    0: give up without looking)."""
+    _check(load_library().lccrf_set_pair_poll_limit(int(polls)), "lccrf_set_pair_poll_limit")
 
 
 def auto_algo(op: int, B: int, N: int, T: int) -> int:
@@ -408,3 +421,17 @@ def lccrf_marginals_timed(phi: torch.Tensor, lengths: Optional[torch.Tensor], ou
                                        logZ.data_ptr(), out.data_ptr(), workspace.data_ptr(),
                                        workspace.numel(), _stream(phi.device), algo, *handles)
     _check(rc, "lccrf_marginals_timed")
+
+
+def lccrf_stream_probe(src: torch.Tensor, dst: Optional[torch.Tensor], workgroups: int, sink: torch.Tensor) -> int:
+    """Benchmark instrumentation: `workgroups` workgroups stream `src` (read only, or copied to `dst`); returns the
+    bytes covered.  Enqueued on the current stream; the caller times it."""
+    lib = load_library()
+    nbytes = src.numel() * src.element_size()
+    if dst is not None and dst.numel() * dst.element_size() < nbytes:
+        raise ValueError("dst is smaller than src")
+    with torch.cuda.device(src.device):
+        rc = lib.lccrf_stream_probe(src.data_ptr(), None if dst is None else dst.data_ptr(), nbytes, int(workgroups),
+                                    sink.data_ptr(), _stream(src.device))
+    _check(rc, "lccrf_stream_probe")
+    return int(lib.lccrf_stream_probe_bytes(nbytes, int(workgroups)))

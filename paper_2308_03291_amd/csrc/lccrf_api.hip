@@ -1,8 +1,10 @@
 // C ABI of the library (declared in include/lccrf.h): argument checks, workspace carving,
 // choice of schedule, launches.  No allocation, no synchronisation, no host copies.
 #include "../../include/lccrf.h"
+#include "../../include/lccrf_instrument.h"
 #include "lccrf_launch.h"
 
+#include <atomic>
 #include <mutex>
 
 // Built-in scratch of lccrf_marginals_static: device memory inside the library's code object, one
@@ -13,8 +15,22 @@ static __device__ __align__(256) unsigned char scratch[LCCRF_STATIC_SCRATCH_BYTE
 
 namespace {
 
-// Device address of `scratch` on the current device, looked up once per device.
 constexpr int kMaxDevices = 64;
+
+// Compute units of the current device (the device the caller's stream belongs to), asked once per device.
+std::atomic<int> g_device_cus[kMaxDevices];
+int current_device_cus() {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return 0;
+    int n = g_device_cus[dev].load(std::memory_order_relaxed);
+    if (n == 0) {
+        if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) n = 0;
+        g_device_cus[dev].store(n, std::memory_order_relaxed);
+    }
+    return n;
+}
+
+// Device address of `scratch` on the current device, looked up once per device.
 std::mutex g_scratch_mutex;
 void* g_scratch_ptr[kMaxDevices] = {};
 void* static_scratch() {
@@ -32,14 +48,32 @@ void* static_scratch() {
 constexpr size_t kAlign = 256;
 inline size_t round_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 
-// Positions per chunk of the chunked scan (lccrf_set_scan_chunk).
-// Positions per chunk of the scan.  0: chosen by shape, the smallest of 8, 16 and 32 that keeps the
+// The two process-wide tuning knobs (atomics: a reader sees the old or the new value, never a torn one).
+// Polls a workgroup of the paired second pass waits for its partner (lccrf_set_pair_poll_limit).  A poll
+// is one round trip to the L2 cache, a few hundred nanoseconds: the default bounds a wait to some tens
+// of milliseconds, four orders of magnitude above an exchange between resident partners (under 1 us).
+constexpr int kDefaultPairPollLimit = 1 << 15;
+std::atomic<int> g_pair_poll_limit{kDefaultPairPollLimit};
+// Positions per chunk of the scan (lccrf_set_scan_chunk).  0: chosen by shape, the smallest of 8, 16 and 32 that keeps the
 // chunks of the batch (one wave each in the scan's first phase) within what the chip holds at once
 // (measured: short chunks win, 8 by 2.8 times on the marginals of B=1, N=128, T=32 against the
 // sequential schedule, until the chunks outnumber the SIMDs, resp. twice their number at 16 tags).
-int g_scan_chunk_user = 0;
+std::atomic<int> g_scan_chunk_user{0};
+// An entry point reads the knob once (KnobSnapshot at its top) and every use inside the call, from sizing
+// the workspace to the last launch, sees that one value, whatever another thread sets meanwhile.
+thread_local int t_snapshot_depth = 0;
+thread_local int t_scan_chunk_user = 0;
+struct KnobSnapshot {
+    KnobSnapshot() {
+        if (t_snapshot_depth++ == 0) t_scan_chunk_user = g_scan_chunk_user.load(std::memory_order_relaxed);
+    }
+    ~KnobSnapshot() { --t_snapshot_depth; }
+    KnobSnapshot(const KnobSnapshot&) = delete;
+    KnobSnapshot& operator=(const KnobSnapshot&) = delete;
+};
 inline int scan_chunk(long long B, long long N, long long T) {
-    if (g_scan_chunk_user) return g_scan_chunk_user;
+    if (const int user = t_snapshot_depth > 0 ? t_scan_chunk_user : g_scan_chunk_user.load(std::memory_order_relaxed))
+        return user;
     const long long cap = T > 16 ? 1024 : 2048;
     for (int c = 8; c < 32; c *= 2)
         if (B * ((N + c - 1) / c) <= cap) return c;
@@ -212,7 +246,8 @@ int sum_query(int op, const void* phi, int dt, const int32_t* lengths, int B, in
         reinterpret_cast<double*>(base + w.Oa), reinterpret_cast<double*>(base + w.Ob), logZ, marginals, st,
         static_cast<hipEvent_t>(ev_between), algo == LCCRF_ALGO_SEQUENTIAL_EXACT,
         algo == LCCRF_ALGO_AUTO ? reinterpret_cast<unsigned long long*>(base + w.mail) : nullptr,
-        reinterpret_cast<int*>(base + w.failed));
+        reinterpret_cast<int*>(base + w.failed), nullptr, nullptr, nullptr,
+        g_pair_poll_limit.load(std::memory_order_relaxed), algo == LCCRF_ALGO_AUTO ? current_device_cus() : 0);
     if (e != hipSuccess) return LCCRF_ELAUNCH;
     if (ev_end && hipEventRecord(static_cast<hipEvent_t>(ev_end), st) != hipSuccess) return LCCRF_ELAUNCH;
     return LCCRF_OK;
@@ -223,6 +258,7 @@ int sum_query(int op, const void* phi, int dt, const int32_t* lengths, int B, in
 extern "C" {
 
 size_t lccrf_workspace_bytes(lccrf_op op, int B, int N, int T, lccrf_dtype dt) {
+    const KnobSnapshot knobs;
     if (!shape_ok(B, N, T) || !dtype_ok(dt)) return 0;
     switch (op) {
         case LCCRF_OP_LOGZ:
@@ -237,6 +273,7 @@ size_t lccrf_workspace_bytes(lccrf_op op, int B, int N, int T, lccrf_dtype dt) {
 }
 
 int lccrf_auto_algo(lccrf_op op, int B, int N, int T) {
+    const KnobSnapshot knobs;
     if (!shape_ok(B, N, T)) return LCCRF_EINVAL;
     bool scan;
     switch (op) {
@@ -254,17 +291,20 @@ int lccrf_auto_algo(lccrf_op op, int B, int N, int T) {
 
 int lccrf_log_partition_algo(const void* phi, lccrf_dtype dt, const int32_t* lengths, int B, int N, int T,
                              float* logZ, void* workspace, size_t workspace_bytes, void* stream, lccrf_algo algo) {
+    const KnobSnapshot knobs;
     return sum_query(0, phi, dt, lengths, B, N, T, logZ, nullptr, workspace, workspace_bytes, stream, algo);
 }
 
 int lccrf_marginals_algo(const void* phi, lccrf_dtype dt, const int32_t* lengths, int B, int N, int T, float* logZ,
                          float* marginals, void* workspace, size_t workspace_bytes, void* stream, lccrf_algo algo) {
+    const KnobSnapshot knobs;
     return sum_query(1, phi, dt, lengths, B, N, T, logZ, marginals, workspace, workspace_bytes, stream, algo);
 }
 
 int lccrf_marginals_timed(const void* phi, lccrf_dtype dt, const int32_t* lengths, int B, int N, int T, float* logZ,
                           float* marginals, void* workspace, size_t workspace_bytes, void* stream, lccrf_algo algo,
                           void* ev_begin, void* ev_between, void* ev_end) {
+    const KnobSnapshot knobs;
     return sum_query(1, phi, dt, lengths, B, N, T, logZ, marginals, workspace, workspace_bytes, stream, algo,
                      ev_begin, ev_between, ev_end);
 }
@@ -272,6 +312,7 @@ int lccrf_marginals_timed(const void* phi, lccrf_dtype dt, const int32_t* length
 int lccrf_argmax_algo(const void* phi, lccrf_dtype dt, const int32_t* lengths, int B, int N, int T,
                       float* best_score, int32_t* tags, void* workspace, size_t workspace_bytes, void* stream,
                       lccrf_algo algo) {
+    const KnobSnapshot knobs;
     const size_t need = lccrf_workspace_bytes(LCCRF_OP_ARGMAX, B, N, T, dt);
     const int rc = check_common(phi, dt, B, N, T, workspace, workspace_bytes, need, algo);
     if (rc != LCCRF_OK) return rc;
@@ -316,6 +357,7 @@ size_t lccrf_static_scratch_bytes(void) { return LCCRF_STATIC_SCRATCH_BYTES; }
 
 int lccrf_marginals_static(const void* phi, lccrf_dtype dt, const int32_t* lengths, int B, int N, int T, float* logZ,
                            float* marginals, void* stream) {
+    const KnobSnapshot knobs;
     const size_t need = lccrf_workspace_bytes(LCCRF_OP_MARGINALS, B, N, T, dt);
     if (need == 0) return LCCRF_EINVAL;
     if (need > LCCRF_STATIC_SCRATCH_BYTES) return LCCRF_ETOOBIG;
@@ -351,6 +393,7 @@ static hipError_t launch_log_partition64(const void* phi, int dt, const int32_t*
 
 int lccrf_log_prob(const void* phi, lccrf_dtype dt, const int32_t* lengths, const int32_t* tags, int B, int N, int T,
                    float* log_prob, void* workspace, size_t workspace_bytes, void* stream) {
+    const KnobSnapshot knobs;
     const size_t need = lccrf_workspace_bytes(LCCRF_OP_LOG_PROB, B, N, T, dt);
     const int rc = check_common(phi, dt, B, N, T, workspace, workspace_bytes, need, LCCRF_ALGO_AUTO);
     if (rc != LCCRF_OK) return rc;
@@ -367,6 +410,7 @@ int lccrf_log_prob(const void* phi, lccrf_dtype dt, const int32_t* lengths, cons
 
 int lccrf_entropy(const void* phi, lccrf_dtype dt, const int32_t* lengths, int B, int N, int T, float* entropy,
                   void* workspace, size_t workspace_bytes, void* stream) {
+    const KnobSnapshot knobs;
     const size_t need = lccrf_workspace_bytes(LCCRF_OP_ENTROPY, B, N, T, dt);
     const int rc = check_common(phi, dt, B, N, T, workspace, workspace_bytes, need, LCCRF_ALGO_AUTO);
     if (rc != LCCRF_OK) return rc;
@@ -409,6 +453,7 @@ int lccrf_entropy(const void* phi, lccrf_dtype dt, const int32_t* lengths, int B
 
 static int cross_query(bool kl, const void* phi_p, const void* phi_q, lccrf_dtype dt, const int32_t* lengths, int B, int N,
                        int T, float* out, void* workspace, size_t workspace_bytes, void* stream) {
+    const KnobSnapshot knobs;
     const size_t need = lccrf_workspace_bytes(LCCRF_OP_CROSS_ENTROPY, B, N, T, dt);
     const int rc = check_common(phi_p, dt, B, N, T, workspace, workspace_bytes, need, LCCRF_ALGO_AUTO);
     if (rc != LCCRF_OK) return rc;
@@ -477,6 +522,7 @@ int lccrf_semi_markov_log_partition(const void* phi, lccrf_dtype dt, const int32
 
 int lccrf_sample(const void* phi, lccrf_dtype dt, const int32_t* lengths, const float* uniforms, int B, int N, int T,
                  int32_t* tags, void* workspace, size_t workspace_bytes, void* stream) {
+    const KnobSnapshot knobs;
     const size_t need = lccrf_workspace_bytes(LCCRF_OP_SAMPLE, B, N, T, dt);
     const int rc = check_common(phi, dt, B, N, T, workspace, workspace_bytes, need, LCCRF_ALGO_AUTO);
     if (rc != LCCRF_OK) return rc;
@@ -523,6 +569,7 @@ static int check_structured(const float* emit, const float* trans, const int32_t
 
 static int structured_sum(int op, const float* emit, const float* trans, const int32_t* lengths, int B, int N, int T,
                           float* logZ, float* marginals, void* workspace, size_t workspace_bytes, void* stream) {
+    const KnobSnapshot knobs;
     const size_t need = lccrf_workspace_bytes(op == 0 ? LCCRF_OP_LOGZ : LCCRF_OP_MARGINALS, B, N, T, LCCRF_F32);
     const int rc = check_structured(emit, trans, lengths, B, N, T, workspace, workspace_bytes, need);
     if (rc != LCCRF_OK) return rc;
@@ -551,6 +598,7 @@ int lccrf_marginals_structured(const float* emit, const float* trans, const int3
 
 int lccrf_argmax_structured(const float* emit, const float* trans, const int32_t* lengths, int B, int N, int T,
                             float* best_score, int32_t* tags, void* workspace, size_t workspace_bytes, void* stream) {
+    const KnobSnapshot knobs;
     const size_t need = lccrf_workspace_bytes(LCCRF_OP_ARGMAX, B, N, T, LCCRF_F32);
     const int rc = check_structured(emit, trans, lengths, B, N, T, workspace, workspace_bytes, need);
     if (rc != LCCRF_OK) return rc;
@@ -581,10 +629,16 @@ const char* lccrf_strerror(int code) {
 
 int lccrf_set_scan_chunk(int chunk) {
     if (chunk != 0 && (chunk < 4 || chunk > 4096)) return LCCRF_EINVAL;
-    g_scan_chunk_user = chunk;
+    g_scan_chunk_user.store(chunk, std::memory_order_relaxed);
     return LCCRF_OK;
 }
 
-int lccrf_version(void) { return 107; }
+int lccrf_set_pair_poll_limit(int polls) {
+    if (polls < -1 || polls > (1 << 24)) return LCCRF_EINVAL;
+    g_pair_poll_limit.store(polls < 0 ? kDefaultPairPollLimit : polls, std::memory_order_relaxed);
+    return LCCRF_OK;
+}
+
+int lccrf_version(void) { return 200; }
 
 }  // extern "C"

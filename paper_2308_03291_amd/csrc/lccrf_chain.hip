@@ -828,6 +828,7 @@ struct PairPlan {
     unsigned long long* mail;
     int* failed;
     int dtype;
+    int poll_limit;
 };
 
 template <typename G, typename TIN, bool ALIGNED, int PF1, int PF2>
@@ -856,7 +857,7 @@ static hipError_t launch_geo(int op, ChainArgs a, hipStream_t st, hipEvent_t bet
         // two workgroups per chain, speculative steps only; whatever they flag as failed is redone below
         // (the first pass above has cleared the mailboxes and the flags: a.pair_mail)
         e = launch_pair_marginals(pair.dtype, a.phi, a.lengths, a.B, a.N, a.T, a.ua, a.ub, a.Oa, a.Ob, a.logZ, a.mu,
-                                  pair.mail, pair.failed, st);
+                                  pair.mail, pair.failed, pair.poll_limit, st);
         if (e != hipSuccess) return e;
         a.only_failed = pair.failed;
     }
@@ -915,7 +916,7 @@ hipError_t launch_full_forward(int dtype, const void* phi, const int32_t* length
     ChainArgs a{phi, lengths, B, N, T, ua, ub, Oa, Ob, nullptr, nullptr, 0, nullptr, 0, 1, nullptr, nullptr, nullptr, nullptr};
     a.full_forward = 1;
     if (wave_supported(T)) return launch_wave(2, dtype, a, st, nullptr);
-    const PairPlan pair{nullptr, nullptr, dtype};
+    const PairPlan pair{nullptr, nullptr, dtype, 0};
     const bool aligned = (T % 4) == 0;
     if (dtype == 0)
         return aligned ? launch_T<float, true>(2, a, st, nullptr, pair) : launch_T<float, false>(2, a, st, nullptr, pair);
@@ -936,7 +937,8 @@ hipError_t launch_chunked_full_forward(int dtype, const void* phi, const int32_t
 hipError_t launch_sequential_sum(int op, int dtype, const void* phi, const int32_t* lengths, int B, int N, int T,
                                  float* ua, float* ub, double* Oa, double* Ob, float* logZ, float* mu,
                                  hipStream_t st, hipEvent_t between, bool exact_only, unsigned long long* mail,
-                                 int* failed, double* logZ64, const float* emit, const float* trans) {
+                                 int* failed, double* logZ64, const float* emit, const float* trans, int pair_poll_limit,
+                                 int cus) {
     ChainArgs a{phi, lengths, B, N, T, ua, ub, Oa, Ob, logZ, mu, exact_only ? 1 : 0, nullptr, 0, 1, nullptr, nullptr, nullptr, nullptr};
     a.logZ64 = logZ64;
     a.emit = emit;
@@ -960,13 +962,8 @@ hipError_t launch_sequential_sum(int op, int dtype, const void* phi, const int32
     if (wave_supported(T)) return launch_wave(op, dtype, a, st, between);
     if (emit) return (T % 4) == 0 ? launch_structured_64<true>(op, a, st, between) : launch_structured_64<false>(op, a, st, between);
     // Pairs pay off when one workgroup per chain would leave at least half of the chip idle.
-    static const int cus = [] {
-        int dev = 0, n = 0;
-        if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) n = 0;
-        return n;
-    }();
     const bool use_pairs = op == 1 && !exact_only && mail && failed && pair_supported(T) && 4 * B <= cus;
-    const PairPlan pair{use_pairs ? mail : nullptr, failed, dtype};
+    const PairPlan pair{use_pairs ? mail : nullptr, failed, dtype, pair_poll_limit};
     if (use_pairs) {
         a.pair_mail = mail;
         a.pair_failed = failed;
@@ -1000,7 +997,7 @@ hipError_t launch_chunked_marginals(int dtype, const void* phi, const int32_t* l
         return launch_wave_chunks(dtype, a, st);
     }
     if (wave_supported(T)) return launch_wave(1, dtype, a, st, between);
-    const PairPlan pair{nullptr, nullptr, dtype};
+    const PairPlan pair{nullptr, nullptr, dtype, 0};
     const bool aligned = (T % 4) == 0;
     if (dtype == 0)
         return aligned ? launch_T<float, true>(1, a, st, between, pair) : launch_T<float, false>(1, a, st, between, pair);

@@ -13,12 +13,15 @@ namespace lccrf {
 // `between`, if non-null, is recorded on `st` after the first pass.  exact_only: skip the
 // speculative uniform-shift step and run the exact step at every position.
 // mail / failed: scratch of the paired second pass (pair_mail_words(B) 8-byte words and B ints),
-// or null to always use one workgroup per chain.
+// or null to always use one workgroup per chain; pair_poll_limit: how many polls a paired workgroup
+// waits for its partner before the sequence goes to the one-workgroup kernel; cus: compute units of
+// the device the stream belongs to (pairs are used when they fit the chip all at once).
 hipError_t launch_sequential_sum(int op, int dtype, const void* phi, const int32_t* lengths, int B, int N, int T,
                                  float* ua, float* ub, double* Oa, double* Ob, float* logZ, float* mu,
                                  hipStream_t st, hipEvent_t between = nullptr, bool exact_only = false,
                                  unsigned long long* mail = nullptr, int* failed = nullptr, double* logZ64 = nullptr,
-                                 const float* emit = nullptr, const float* trans = nullptr);
+                                 const float* emit = nullptr, const float* trans = nullptr, int pair_poll_limit = 0,
+                                 int cus = 0);
 // Sampling (lccrf_chain.hip, lccrf_extras.hip): forward chains over whole sequences with every alpha
 // stored, then the backward sweep that draws the tags from the given uniforms [B][N].
 hipError_t launch_full_forward(int dtype, const void* phi, const int32_t* lengths, int B, int N, int T, float* ua,
@@ -40,7 +43,8 @@ size_t pair_mail_words(int B);
 bool pair_supported(int T);
 hipError_t launch_pair_marginals(int dtype, const void* phi, const int32_t* lengths, int B, int N, int T,
                                  const float* ua, const float* ub, const double* Oa, const double* Ob,
-                                 float* logZ, float* mu, unsigned long long* mail, int* failed, hipStream_t st);
+                                 float* logZ, float* mu, unsigned long long* mail, int* failed, int poll_limit,
+                                 hipStream_t st);
 
 // Chunked scan over positions (lccrf_scan.hip), tag sets of at most 32 (TP = 16 or 32 padded tags).  Writes, per chunk of `chunk`
 // positions (C = ceil(N / chunk) chunks per sequence), the chunk's transfer matrix (Pl: TP^2 floats, rel: TP

@@ -20,7 +20,10 @@
 // accepted range, whose sequence has no finite path, or whose partner does not answer within
 // a bounded number of polls marks the sequence as failed and stops; the one-workgroup exact
 // kernel then recomputes the failed sequences.  Correctness therefore never depends on both
-// partners being resident at the same time, only the speed does.
+// partners being resident at the same time, only the speed does (and the low-order bits: the exact
+// kernel rounds differently from the pair, so a hand-over that depends on timing makes two runs
+// differ within the tolerance).  A receiver that finds its sequence flagged stops at its next poll,
+// so one expired wait ends all four workgroups of the sequence within a poll's time.
 // Measured on this kernel: the folded DPP forms and the mirror step make the second pass 1-2 % slower
 // (0.925 against 0.908 ms on config 4), although they are fewer instructions; the plain forms stay here.
 #define LCCRF_LANE_EXCHANGE_CLASSIC
@@ -35,7 +38,6 @@ constexpr int kPairW = 512;        // threads that load and compute (8 waves)
 constexpr int kPairWaves = 8;
 constexpr int kPairThreads = kPairW + 64;  // plus one wave that only receives the partner's half
 constexpr int kPairPF = 4;         // tiles in the register ring
-constexpr int kPollLimit = 1 << 18;
 constexpr int kPairMailWords = 128;  // words per mailbox slot (one per entry of a half vector, T <= 256)
 
 // One mailbox word: [tag:16][extra:16][value:32], written and read as one 8-byte access, so a
@@ -56,6 +58,7 @@ struct PairArgs {
     float* mu;
     unsigned long long* mail;  // [2B chains][2 partners][2 slots][kPairMailWords]
     int* failed;               // [B]
+    int poll_limit;            // polls a receiver waits for its partner's words before it gives the sequence up
 };
 
 template <int T>
@@ -89,28 +92,25 @@ __device__ __forceinline__ void send_half(unsigned long long* mine, unsigned tag
 // Receiver side, executed by the extra wave only: polls the partner's words of this step,
 // puts the partner's half into vec[nbuf] and its scalars into shared memory.  Sets sm.stop if
 // the partner rejected the step, if the sequence has been flagged as failed, or if nothing
-// arrives within kPollLimit polls.
+// arrives within poll_limit looks (0: gives up without looking).
 template <int T>
 __device__ __forceinline__ void receive_half(PairSmem<T>& sm, const unsigned long long* theirs, const int* failed_flag,
-                                             unsigned tag, int lane, int nbuf, int p) {
+                                             unsigned tag, int lane, int nbuf, int p, int poll_limit) {
     constexpr int H = T / 2;
     constexpr int NQ = H / 64;
     const unsigned long long* in = theirs + (tag & 1) * kPairMailWords;
     unsigned long long w[NQ];
     bool ok = false;
-    int spins = 0;
-    while (true) {
+    // at most poll_limit looks (the limit is a kernel argument, the same in every lane): the wait always ends
+    for (int looks = 0; looks < poll_limit; ++looks) {
         ok = true;
 #pragma unroll
         for (int q = 0; q < NQ; ++q) {
             w[q] = __hip_atomic_load(&in[lane + 64 * q], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             ok = ok && (unsigned)(w[q] >> 48) == (tag & 0xffffu);
         }
-        if (__all(ok)) break;
-        if (++spins > kPollLimit || __hip_atomic_load(failed_flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0) {
-            ok = false;
-            break;
-        }
+        ok = __all(ok);
+        if (ok || __hip_atomic_load(failed_flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0) break;
     }
     if (!__all(ok)) {
         if (lane == 0) sm.stop = 1;
@@ -214,7 +214,7 @@ __global__ __launch_bounds__(kPairThreads) void pair_marginal_kernel(PairArgs a)
         int buf = 0;
         for (int done = 0; done < n; ++done) {
             __syncthreads();  // A
-            receive_half<T>(sm, theirs, failed, (unsigned)(done + 1), lane, buf ^ 1, p);
+            receive_half<T>(sm, theirs, failed, (unsigned)(done + 1), lane, buf ^ 1, p, a.poll_limit);
             __syncthreads();  // B
             buf ^= 1;
             if (sm.stop != 0) return;
@@ -423,8 +423,9 @@ bool pair_supported(int T) { return T == 128; }
 
 hipError_t launch_pair_marginals(int dtype, const void* phi, const int32_t* lengths, int B, int N, int T,
                                  const float* ua, const float* ub, const double* Oa, const double* Ob,
-                                 float* logZ, float* mu, unsigned long long* mail, int* failed, hipStream_t st) {
-    PairArgs a{phi, lengths, B, N, ua, ub, Oa, Ob, logZ, mu, mail, failed};
+                                 float* logZ, float* mu, unsigned long long* mail, int* failed, int poll_limit,
+                                 hipStream_t st) {
+    PairArgs a{phi, lengths, B, N, ua, ub, Oa, Ob, logZ, mu, mail, failed, poll_limit};
     const int chains = 2 * B;
     const int grid = ((chains + 7) / 8) * 16;
     if (T == 128) {

@@ -20,16 +20,21 @@ def lib():
 
 
 def _declared_functions():
-    text = open(os.path.join(ROOT, "include", "lccrf.h")).read()
-    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(lccrf_[a-z_]+)\s*\(", text)))
+    """Every function declared in any header under include/."""
+    names = set()
+    inc = os.path.join(ROOT, "include")
+    for f in sorted(os.listdir(inc)):
+        if f.endswith(".h"):
+            text = re.sub(r"/\*.*?\*/", "", open(os.path.join(inc, f)).read(), flags=re.S)
+            names |= set(re.findall(r"\b(lccrf_[a-z_0-9]+)\s*\(", text))
+    return sorted(names)
 
 
 def test_every_declared_symbol_is_exported(lib):
     names = _declared_functions()
     assert "lccrf_log_partition" in names and "lccrf_marginals" in names and "lccrf_argmax" in names
     for n in names:
-        assert hasattr(lib, n), f"{n} is declared in include/lccrf.h but not exported"
+        assert hasattr(lib, n), f"{n} is declared under include/ but not exported"
     assert set(names) == set(binding.EXPORTS)
 
 
@@ -89,6 +94,22 @@ def test_bad_arguments_are_rejected_without_a_gpu(lib):
     assert lib.lccrf_marginals(fake, 0, None, 1, 4, 4, None, fake + 4, fake, ws, None) == EALIGN
     assert lib.lccrf_argmax(fake, 0, None, 1, 4, 4, None, None, fake, ws, None) == ENULL
     assert lib.lccrf_argmax_algo(fake, 0, None, 1, 4, 4, None, fake, fake, ws, None, 17) == EINVAL
+
+
+def test_tuning_knobs_check_their_range(lib):
+    assert lib.lccrf_set_scan_chunk(3) == -1 and lib.lccrf_set_scan_chunk(5000) == -1
+    assert lib.lccrf_set_scan_chunk(0) == 0
+    assert lib.lccrf_set_pair_poll_limit(-2) == -1 and lib.lccrf_set_pair_poll_limit((1 << 24) + 1) == -1
+    assert lib.lccrf_set_pair_poll_limit(0) == 0 and lib.lccrf_set_pair_poll_limit(-1) == 0
+    # the chunk enters the workspace size: a call sized under one setting is refused under a larger need
+    small = binding.workspace_bytes(binding.OP_MARGINALS, 2, 4096, 16, 0)
+    assert lib.lccrf_set_scan_chunk(4) == 0
+    try:
+        assert binding.workspace_bytes(binding.OP_MARGINALS, 2, 4096, 16, 0) > small
+        fake = 4096
+        assert lib.lccrf_marginals(fake, 0, None, 2, 4096, 16, fake, fake, fake, small, None) == -3
+    finally:
+        assert lib.lccrf_set_scan_chunk(0) == 0
 
 
 def test_binding_refuses_cpu_tensors():

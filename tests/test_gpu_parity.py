@@ -410,3 +410,72 @@ def test_paper_hmm_shape(crf, oracle_mod):
     leaves all parallelism to the two chains."""
     w = workloads.WORKLOADS["paper_hmm"]
     check_case(crf, oracle_mod, workloads.phi_batch(w), workloads.lengths(w), what="paper hmm shape")
+
+
+def test_paired_second_pass_gives_up_when_the_wait_expires(crf, oracle_mod):
+    """The bounded wait of the paired pass, made to expire from the host: with a poll limit of 0 every
+    receiver gives up without looking, all four workgroups of every sequence stop, and the one-workgroup
+    kernel recomputes the whole batch.  Every kernel exits normally; the results equal the oracle's and,
+    bit for bit, those of the schedule that never uses pairs."""
+    T, N = 128, 40
+    phi, _ = workloads.random_case(4600, 6, N, T, scale=1.3)
+    lens = torch.tensor([40, 39, 2, 17, 1, 0], dtype=torch.int32)
+    dphi, dl = phi.cuda(), lens.cuda()
+    lz_seq, mu_seq = crf.lccrf_marginals(dphi, dl, algo=crf.ALGO_SEQUENTIAL)
+    lz_pair, mu_pair = crf.lccrf_marginals(dphi, dl)
+    crf.set_pair_poll_limit(0)
+    try:
+        check_case(crf, oracle_mod, phi, lens, what="paired, wait expired", queries=("mu",))
+        lz_0, mu_0 = crf.lccrf_marginals(dphi, dl)
+        torch.cuda.synchronize()
+    finally:
+        crf.set_pair_poll_limit(-1)
+    assert torch.equal(mu_0, mu_seq) and torch.equal(lz_0, lz_seq)
+    # with the default limit the pairs do the work: close to, but rounded differently from, the other kernel
+    assert float((mu_pair - mu_seq).abs().max()) < 2e-6
+    assert not torch.equal(mu_pair, mu_seq)
+    lz_again, mu_again = crf.lccrf_marginals(dphi, dl)      # and the default is back in force
+    assert torch.equal(mu_again, mu_pair)
+
+
+def _tie_rule_path(phi64, L, T, h):
+    """Of all best paths (by enumeration), the one with the smallest tag at h, then at h-1, ..., 0, then at
+    h+1, ..., L-1: the documented choice of the sequential schedule among exactly tied paths."""
+    from oracle import brute
+    paths = brute.all_paths(T, L)
+    sc = brute.path_scores(phi64, L, paths)
+    best = paths[sc == sc.max()]
+    for i in [h] + list(range(h - 1, -1, -1)) + list(range(h + 1, L)):
+        best = best[best[:, i] == best[:, i].min()]
+    assert best.shape[0] == 1
+    return best[0], float(sc.max())
+
+
+@pytest.mark.parametrize("T,L", [(2, 4), (2, 9), (3, 7), (4, 6), (5, 5)])
+def test_exactly_tied_best_paths_follow_the_documented_rule(crf, T, L):
+    """Small integer potentials: many paths tie exactly (the sums are exact in any order).  The sequential
+    schedule must return the path the header documents; the case T=2, L=4 with tied optima (0,0,1,0) and
+    (0,0,0,1) tells that rule from "smallest tag from the back"."""
+    N = L + 2
+    g = torch.Generator().manual_seed(700 + 10 * T + L)
+    B = 24
+    phi = torch.randint(-1, 2, (B, N, T, T), generator=g).to(torch.float32)
+    if (T, L) == (2, 4):
+        phi[0] = 0.0
+        phi[0, 1] = torch.tensor([[1.0, 0.0], [0.0, 0.0]])   # y0 = y1 = 0
+        phi[0, 2] = torch.tensor([[1.0, 1.0], [0.0, 0.0]])   # y1 = 0, y2 free
+        phi[0, 3] = torch.tensor([[0.0, 1.0], [1.0, 0.0]])   # y3 != y2
+        phi[0, 0, 0] = torch.tensor([1.0, 0.0])
+    lens = torch.full((B,), L, dtype=torch.int32)
+    lens[1] = L - 1
+    score, tags = crf.lccrf_argmax(phi.cuda(), lens.cuda(), algo=crf.ALGO_SEQUENTIAL)
+    score, tags = score.cpu().numpy(), tags.cpu().numpy()
+    ties = 0
+    for b in range(B):
+        Lb = int(lens[b])
+        want, best = _tie_rule_path(phi[b].numpy().astype(np.float64), Lb, T, Lb // 2)
+        assert score[b] == best
+        assert np.array_equal(tags[b, :Lb], want), f"sequence {b}: {tags[b, :Lb]} vs {want}"
+        assert (tags[b, Lb:] == -1).all()
+    if (T, L) == (2, 4):
+        assert list(tags[0, :4]) == [0, 0, 0, 1]
