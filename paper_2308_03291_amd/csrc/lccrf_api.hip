@@ -74,7 +74,10 @@ struct KnobSnapshot {
 inline int scan_chunk(long long B, long long N, long long T) {
     if (const int user = t_snapshot_depth > 0 ? t_scan_chunk_user : g_scan_chunk_user.load(std::memory_order_relaxed))
         return user;
-    const long long cap = T > 16 ? 1024 : 2048;
+    // 33 .. 64 tags: a chunk's product takes a workgroup of three or four waves that fills a compute unit, so
+    // the chunks should not outnumber the compute units (measured: B=1, N=128, T=48 is best at 8, B=32, N=256
+    // and B=8, N=1024 at 32)
+    const long long cap = T > 32 ? 256 : T > 16 ? 1024 : 2048;
     for (int c = 8; c < 32; c *= 2)
         if (B * ((N + c - 1) / c) <= cap) return c;
     return 32;
@@ -191,6 +194,10 @@ int check_common(const void* phi, int dt, int B, int N, int T, const void* ws, s
 // own benchmark size, 128 x 256, is the limit).
 inline bool scan_pays_sum(int B, int N, int T) {
     if (!lccrf::scan_supported(T) || N < 8 * scan_chunk(B, N, T)) return false;
+    // 33 .. 64 tags: a position of a chunk product costs a compute unit about 2.4 us (36 to 64 matrix
+    // instructions a wave beside as many exponentials), which the shorter chains pay back up to about 8192
+    // positions a batch (B=32, N=256, T=48: marginals 285 -> 124 us; B=128, N=128, T=48: 148 -> 206 us).
+    if (T > 32) return (long long)B * N <= 8192;
     return T <= 16 ? B <= 448 : (long long)B * N <= 32768;
 }
 // The max-plus scan (16 tags at most) pays its chunk products in double-precision vector
@@ -202,8 +209,10 @@ inline bool scan_pays_max(int B, int N, int T) {
 // The entropy-like queries make two passes under the scan against one sequential pass: with 17 .. 32
 // tags it takes chains twice as long to pay.
 inline bool scan_pays_entropy(int B, int N, int T) {
-    return scan_pays_sum(B, N, T) && (T <= 16 || N >= 16 * scan_chunk(B, N, T));
+    return T <= 32 && scan_pays_sum(B, N, T) && (T <= 16 || N >= 16 * scan_chunk(B, N, T));
 }
+// Sampling under the scan runs every chunk's forward chain with the one-wave kernels (32 tags at most).
+inline bool scan_pays_sample(int B, int N, int T) { return T <= 32 && scan_pays_sum(B, N, T); }
 
 int sum_query(int op, const void* phi, int dt, const int32_t* lengths, int B, int N, int T, float* logZ,
               float* marginals, void* workspace, size_t workspace_bytes, void* stream, int algo,
@@ -279,8 +288,8 @@ int lccrf_auto_algo(lccrf_op op, int B, int N, int T) {
     switch (op) {
         case LCCRF_OP_LOGZ:
         case LCCRF_OP_MARGINALS:
-        case LCCRF_OP_LOG_PROB:
-        case LCCRF_OP_SAMPLE: scan = scan_pays_sum(B, N, T); break;
+        case LCCRF_OP_LOG_PROB: scan = scan_pays_sum(B, N, T); break;
+        case LCCRF_OP_SAMPLE: scan = scan_pays_sample(B, N, T); break;
         case LCCRF_OP_ARGMAX: scan = scan_pays_max(B, N, T); break;
         case LCCRF_OP_ENTROPY:
         case LCCRF_OP_CROSS_ENTROPY: scan = scan_pays_entropy(B, N, T); break;
@@ -536,7 +545,7 @@ int lccrf_sample(const void* phi, lccrf_dtype dt, const int32_t* lengths, const 
     double* Oa = reinterpret_cast<double*>(base + w.Oa);
     double* Ob = reinterpret_cast<double*>(base + w.Ob);
     hipError_t e;
-    if (scan_pays_sum(B, N, T)) {  // alpha everywhere, chunk by chunk from the scan's boundary vectors
+    if (scan_pays_sample(B, N, T)) {  // alpha everywhere, chunk by chunk from the scan's boundary vectors
         float* Fv = reinterpret_cast<float*>(base + w.Fv);
         double* OF = reinterpret_cast<double*>(base + w.OF);
         e = lccrf::launch_scan_boundaries(dt, phi, lengths, B, N, T, scan_chunk(B, N, T), reinterpret_cast<float*>(base + w.Pl),

@@ -1,4 +1,4 @@
-// Chunked log-semiring scan over the positions of long chains with a small tag set (T <= 32; the
+// Chunked log-semiring scan over the positions of long chains with a small tag set (T <= 64; the
 // max-plus variant T <= 16).
 //
 // The paper (section "Sequence Tagging") notes that the forward algorithm can also be run as a
@@ -29,6 +29,8 @@
 // log2 of the scaled product, one integer log2 scale per entry tag and one common offset.
 #include "lccrf_device.h"
 #include "lccrf_launch.h"
+
+#include <type_traits>
 
 namespace lccrf {
 
@@ -84,48 +86,140 @@ __device__ __forceinline__ void chunk_range(int c, int chunk, int L, int& first,
 // ---------------------------------------------------------------------------------------
 // Phase A.
 //
-// TP is the padded tag count (16 or 32); matrices are handled as NB x NB blocks of 16 x 16,
+// TP is the padded tag count (16, 32, 48 or 64); matrices are handled as NB x NB blocks of 16 x 16,
 // NB = TP / 16.  Lane (g = lane / 16, j = lane % 16) handles, of block (sb, tb), four entries of
-// column 16 tb + j (row: tag before, column: tag after), entry number e = (sb NB + tb) 4 + v: the rows
-// an accumulator register v of that lane holds after a 16x16x4 MFMA, which are 16 sb + g + 4v for the
-// f64 instruction (F64) and 16 sb + 4g + v for the f32 one.  Sources hand out matrices in base-2
+// the column at position j of block tb (row: tag before, column: tag after), entry number
+// e = (sb NB + tb) 4 + v: the rows an accumulator register v of that lane holds after a 16x16x4 MFMA,
+// which sit at positions g + 4v of block sb for the f64 instruction (F64) and 4g + v for the f32 one.  Sources hand out matrices in base-2
 // logarithms, -inf outside T x T; every matrix may carry a common offset besides.
+//
+// Up to 32 tags one wave holds the whole running product D.  Above, a workgroup of NB waves serves a
+// chunk and wave w holds block column w of D (the entry tags 16 w .. 16 w + 15): a block column of
+// D_new = E^T D needs all of E but only its own columns of D, so every wave reads the whole matrix of
+// a position (and exponentiates it: the same T^2 exponentials a wave, on four SIMDs at once), issues
+// a quarter of the matrix instructions and keeps a quarter of the product in registers, and the waves
+// exchange nothing until the product is complete.
 template <int TP, bool F64 = true>
 struct ScanShape {
+    static_assert(TP == 16 || TP == 32 || TP == 48 || TP == 64, "padded tag count");
     static constexpr int NB = TP / 16, NE = 4 * NB * NB;
-    static constexpr int LPRow = 64 / TP;    // lanes sharing a row in the row-wise layouts (exact product, phase B)
-    static constexpr int CPL = TP / LPRow;   // columns per lane there
-    static_assert(TP == 16 || TP == 32, "padded tag count");
+    static constexpr int NW = TP <= 32 ? 1 : NB;  // waves per product
+    static constexpr int RB = NB / NW;            // block columns of D a wave holds
+    static constexpr int LPRow = TP <= 32 ? 64 / TP : 1;  // lanes sharing a row in phase B (one wave per vector)
+    static constexpr int CPL = TP / LPRow;                // columns per lane there
+    static constexpr int XL = 64 * NW / TP;  // threads sharing a row in the exact product (all waves of the workgroup)
+    static constexpr int XC = TP / XL;       // columns per thread there
+    // Tag held by position w (0 .. 15) of block b: blocks are interleaved, tag = NB w + b, so that the NB
+    // columns a lane holds of one row (position j of every block) are neighbours in memory: one vector load
+    // per row instead of NB scalar ones, and the sixteen lanes of a row read one contiguous stretch.
+    static __device__ __forceinline__ int tag(int b, int w) { return NB * w + b; }
     static __device__ __forceinline__ int row(int lane, int e) {
-        return 16 * (e / (4 * NB)) + (F64 ? (lane >> 4) + 4 * (e & 3) : 4 * (lane >> 4) + (e & 3));
+        return tag(e / (4 * NB), F64 ? (lane >> 4) + 4 * (e & 3) : 4 * (lane >> 4) + (e & 3));
     }
-    static __device__ __forceinline__ int col(int lane, int e) { return 16 * ((e / 4) % NB) + (lane & 15); }
+    static __device__ __forceinline__ int col(int lane, int e) { return tag((e / 4) % NB, lane & 15); }
+};
+// One bit per entry a lane holds of a matrix.
+template <int NE>
+using ScanMask = std::conditional_t<(NE > 32), unsigned long long, unsigned>;
+template <typename M>
+__device__ __forceinline__ M shfl_mask(M m, int src) {
+    if constexpr (sizeof(M) == 8) {
+        const unsigned lo = (unsigned)__shfl((int)(unsigned)(m & 0xffffffffull), src, 64);
+        const unsigned hi = (unsigned)__shfl((int)(unsigned)(m >> 32), src, 64);
+        return ((unsigned long long)hi << 32) | lo;
+    } else {
+        return (M)__shfl((int)m, src, 64);
+    }
+}
+// What the waves of one product tell each other when it is complete (one slot per precision tried).
+struct ProductShared {
+    float emax[2][4];
+    int rejected[2][4];
 };
 
-template <typename TIN, int TP, bool F64>
+// NB consecutive elements starting at p (NB = 2, 3 or 4; p aligned to NB elements for 2 and 4, to one for 3).
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef float f32x3 __attribute__((ext_vector_type(3)));
+template <int NB>
+__device__ __forceinline__ void load_row(const float* p, float (&v)[NB]) {
+    if constexpr (NB == 2) {
+        const f32x2 q = *reinterpret_cast<const f32x2*>(p);
+        v[0] = q[0]; v[1] = q[1];
+    } else if constexpr (NB == 3) {
+        struct __attribute__((packed, aligned(4))) Three { float a, b, c; };
+        const Three q = *reinterpret_cast<const Three*>(p);
+        v[0] = q.a; v[1] = q.b; v[2] = q.c;
+    } else {
+        const f32x4 q = *reinterpret_cast<const f32x4*>(p);
+        v[0] = q[0]; v[1] = q[1]; v[2] = q[2]; v[3] = q[3];
+    }
+}
+template <int NB>
+__device__ __forceinline__ void load_row(const uint16_t* p, float (&v)[NB]) {
+    if constexpr (NB == 2) {
+        const unsigned q = *reinterpret_cast<const unsigned*>(p);
+        v[0] = __uint_as_float(q << 16); v[1] = __uint_as_float(q & 0xffff0000u);
+    } else if constexpr (NB == 3) {
+#pragma unroll
+        for (int k = 0; k < 3; ++k) v[k] = bf16_to_f32(p[k]);
+    } else {
+        const uint2 q = *reinterpret_cast<const uint2*>(p);
+        v[0] = __uint_as_float(q.x << 16); v[1] = __uint_as_float(q.x & 0xffff0000u);
+        v[2] = __uint_as_float(q.y << 16); v[3] = __uint_as_float(q.y & 0xffff0000u);
+    }
+}
+
+// VEC: T is a multiple of NB (and, for four-wide loads, of 4): a lane's NB columns of a row are loaded
+// with one instruction.  Otherwise one scalar load per entry.
+template <typename TIN, int TP, bool F64, bool VEC>
 struct PotentialMatrices {  // the potentials phi_i of one sequence
     using S = ScanShape<TP, F64>;
-    static constexpr int PF = TP == 16 ? kScanPF : 3;
+    static constexpr int NB = S::NB;
+    // tiles in flight: the counter of outstanding loads a wave can wait on ends at 63, so a ring of scalar
+    // loads (NE a tile) must stay below that or every step waits for all of them
+    static constexpr int PF = TP == 16 ? kScanPF : TP == 32 ? 3 : VEC ? (TP == 48 ? 3 : 2) : 1;
     struct Slot { float x[S::NE]; };
     // entries outside T x T are loaded from the nearest entry inside: whatever a slot holds is a potential
     static constexpr bool kPaddingIsFinite = true;
     const TIN* phib;
     int T;
     size_t TT;
-    int off[S::NE];
-    unsigned in;  // bit e: entry e lies inside T x T
+    // entry e = (sb NB + tb) 4 + v sits at row offset roff[4 sb + v] plus column coff[tb] (both clamped into the matrix)
+    int roff[4 * NB], coff[NB];
+    ScanMask<S::NE> in;  // bit e: entry e lies inside T x T
     __device__ PotentialMatrices(const TIN* p, int T_, int lane) : phib(p), T(T_), TT((size_t)T_ * T_), in(0) {
 #pragma unroll
         for (int e = 0; e < S::NE; ++e) {
             const int s = S::row(lane, e), t = S::col(lane, e);
-            in |= (s < T && t < T) ? (1u << e) : 0u;
-            off[e] = (s < T ? s : T - 1) * T + (t < T ? t : T - 1);
+            in |= (s < T && t < T) ? (ScanMask<S::NE>(1) << e) : ScanMask<S::NE>(0);
         }
+#pragma unroll
+        for (int k = 0; k < 4 * NB; ++k) {
+            const int s = S::row(lane, (k / 4) * 4 * NB + (k & 3));
+            roff[k] = (s < T ? s : T - 1) * T;
+        }
+#pragma unroll
+        for (int tb = 0; tb < NB; ++tb) {
+            const int t = S::col(lane, 4 * tb);
+            coff[tb] = t < T ? t : T - 1;
+        }
+        // vector loads: the lane's columns NB j .. NB j + NB - 1 (T a multiple of NB: all inside or all outside)
+        if (VEC) coff[0] = coff[0] + NB <= T ? coff[0] : T - NB;
     }
     __device__ __forceinline__ void load(int i, Slot& sl) const {
         const TIN* m = phib + (size_t)i * TT;
+        if constexpr (VEC && NB > 1) {
 #pragma unroll
-        for (int e = 0; e < S::NE; ++e) sl.x[e] = Elem<TIN>::get(m + off[e]);
+            for (int k = 0; k < 4 * NB; ++k) {
+                float v[NB];
+                load_row<NB>(m + roff[k] + coff[0], v);
+#pragma unroll
+                for (int tb = 0; tb < NB; ++tb) sl.x[((k / 4) * NB + tb) * 4 + (k & 3)] = v[tb];
+            }
+        } else {
+#pragma unroll
+            for (int e = 0; e < S::NE; ++e) sl.x[e] = Elem<TIN>::get(m + roff[(e / (4 * NB)) * 4 + (e & 3)] + coff[(e / 4) % NB]);
+        }
     }
     __device__ __forceinline__ double entries(const Slot& sl, float (&x)[S::NE]) const {
 #pragma unroll
@@ -148,7 +242,7 @@ template <int TP, bool F64>
 struct ChunkMatrices {  // the chunk products of one sequence, as phase A has written them
     using S = ScanShape<TP, F64>;
     static constexpr int PF = TP == 16 ? 4 : 2;
-    struct Slot { float p[S::NE], r[S::NE]; double b; };
+    struct Slot { float p[S::NE], r[4 * S::NB]; double b; };  // r: the scale of row 16 sb + (row of register v), at [4 sb + v]
     static constexpr bool kPaddingIsFinite = false;  // stored products are -inf outside T x T
     const float* Pl;
     const float* rel;
@@ -158,16 +252,15 @@ struct ChunkMatrices {  // the chunk products of one sequence, as phase A has wr
         : Pl(Pl_), rel(rel_), base(base_), T(T_), lane(lane_) {}
     __device__ __forceinline__ void load(int c, Slot& sl) const {
 #pragma unroll
-        for (int e = 0; e < S::NE; ++e) {
-            sl.p[e] = Pl[(size_t)c * TP * TP + S::col(lane, e) * TP + S::row(lane, e)];
-            sl.r[e] = rel[(size_t)c * TP + S::row(lane, e)];
-        }
+        for (int e = 0; e < S::NE; ++e) sl.p[e] = Pl[(size_t)c * TP * TP + S::col(lane, e) * TP + S::row(lane, e)];
+#pragma unroll
+        for (int k = 0; k < 4 * S::NB; ++k) sl.r[k] = rel[(size_t)c * TP + S::row(lane, (k / 4) * 4 * S::NB + (k & 3))];
         sl.b = base[c];
     }
     __device__ __forceinline__ double entries(const Slot& sl, float (&x)[S::NE]) const {
 #pragma unroll
         for (int e = 0; e < S::NE; ++e)
-            x[e] = (S::row(lane, e) < T && S::col(lane, e) < T) ? sl.p[e] + sl.r[e] : LCCRF_NEG_INF;
+            x[e] = (S::row(lane, e) < T && S::col(lane, e) < T) ? sl.p[e] + sl.r[(e / (4 * S::NB)) * 4 + (e & 3)] : LCCRF_NEG_INF;
         return sl.b;
     }
     __device__ __forceinline__ float entry(int c, int r, int t) const {
@@ -229,44 +322,49 @@ struct Linear<false> {
 // time, the gain is half as large and the same loss would fall on long chains of peaked
 // potentials, so those stay in double precision.
 template <int TP>
-constexpr bool kSingleFirst = TP == 32;
+constexpr bool kSingleFirst = TP >= 32;
 
 template <int TP, bool F64, typename Src>
 __device__ __forceinline__ bool linear_product(const Src& src, int first, int last, int T, float* __restrict__ Pout,
-                                               float* __restrict__ rel_out, double* __restrict__ base_out) {
+                                               float* __restrict__ rel_out, double* __restrict__ base_out,
+                                               ProductShared& shared) {
     using S = ScanShape<TP, F64>;
     using L = Linear<F64>;
     using scalar = typename L::scalar;
     using vec = typename L::vec;
-    constexpr int NB = S::NB, NE = S::NE;
-    const int lane = threadIdx.x;
+    using Mask = ScanMask<S::NE>;
+    constexpr int NB = S::NB, NE = S::NE, RB = S::RB;
+    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+    const int rb0 = wv * RB;  // this wave holds block columns rb0 .. rb0 + RB - 1 of D
     const int g = lane >> 4, j = lane & 15;
-    unsigned in = 0;
+    Mask in = 0;
 #pragma unroll
-    for (int e = 0; e < NE; ++e) in |= (S::row(lane, e) < T && S::col(lane, e) < T) ? (1u << e) : 0u;
+    for (int e = 0; e < NE; ++e) in |= (S::row(lane, e) < T && S::col(lane, e) < T) ? (Mask(1) << e) : Mask(0);
+    // entry (tb, rb, v) of D lies inside T x T (the numbering of the entries of a matrix, rb in the place of tb)
+    const auto inside = [&](int tb, int rl, int v) { return ((in >> ((tb * NB + rb0 + rl) * 4 + v)) & 1) != 0; };
     // The zero pattern of D (1 where some path exists) is carried along by a product of 0/1
     // matrices on the f32 MFMA, from the first matrix with a -inf entry on (until then D is
     // the identity or has no zero).  That instruction numbers its output rows 4g + v; beside the
     // f64 product it therefore runs on rows renamed by pi(4g + v) = g + 4v: its A operand is the
     // flag of column pi(j).
     const int pj = F64 ? ((lane & 48) | (4 * (j & 3) + (j >> 2))) : lane;
-    scalar D[NB][NB][4];
-    float Z[NB][NB][4];
+    scalar D[NB][RB][4];
+    float Z[NB][RB][4];
     double Msum = 0.0;
-    int esum[NB];
+    int esum[RB];
     bool bad = false, tracking = false, started = false, rejected = false;
 #pragma unroll
     for (int sb = 0; sb < NB; ++sb)
 #pragma unroll
-        for (int rb = 0; rb < NB; ++rb)
+        for (int rl = 0; rl < RB; ++rl)
 #pragma unroll
             for (int v = 0; v < 4; ++v) {
-                const bool diag = sb == rb && (F64 ? g + 4 * v : 4 * g + v) == j;
-                D[sb][rb][v] = diag ? (scalar)1 : (scalar)0;
-                Z[sb][rb][v] = diag ? 1.f : 0.f;
+                const bool diag = sb == rb0 + rl && (F64 ? g + 4 * v : 4 * g + v) == j;
+                D[sb][rl][v] = diag ? (scalar)1 : (scalar)0;
+                Z[sb][rl][v] = diag ? 1.f : 0.f;
             }
 #pragma unroll
-    for (int rb = 0; rb < NB; ++rb) esum[rb] = 0;
+    for (int rl = 0; rl < RB; ++rl) esum[rl] = 0;
     typename Src::Slot ring[Src::PF];
     auto load = [&](int i, int slot) { src.load(i, ring[slot]); };
     // The single-precision product looks at every position whether it still holds, and ends at
@@ -279,11 +377,11 @@ __device__ __forceinline__ bool linear_product(const Src& src, int first, int la
         for (int e = 1; e < NE; ++e) mloc = fmaxf(mloc, x[e]);
         const float m = finite_or_zero(xor_max<1, 64>(mloc));
         Msum += (double)m + common;
-        vec acc[NB][NB];
+        vec acc[NB][RB];
 #pragma unroll
         for (int tb = 0; tb < NB; ++tb)
 #pragma unroll
-            for (int rb = 0; rb < NB; ++rb) acc[tb][rb] = vec{0, 0, 0, 0};
+            for (int rl = 0; rl < RB; ++rl) acc[tb][rl] = vec{0, 0, 0, 0};
 #pragma unroll
         for (int sb = 0; sb < NB; ++sb)
 #pragma unroll
@@ -292,16 +390,16 @@ __device__ __forceinline__ bool linear_product(const Src& src, int first, int la
                 for (int v = 0; v < 4; ++v) {
                     const scalar E = L::pow2(x[(sb * NB + tb) * 4 + v] - m);
 #pragma unroll
-                    for (int rb = 0; rb < NB; ++rb) acc[tb][rb] = L::mfma(E, D[sb][rb][v], acc[tb][rb]);
+                    for (int rl = 0; rl < RB; ++rl) acc[tb][rl] = L::mfma(E, D[sb][rl][v], acc[tb][rl]);
                 }
         // bit e of nz: entry e of this matrix is not a structural zero
         const auto nonzero_mask = [&]() {
-            unsigned nz = 0;
+            Mask nz = 0;
 #pragma unroll
-            for (int e = 0; e < NE; ++e) nz |= (x[e] > LCCRF_NEG_INF) ? (1u << e) : 0u;
+            for (int e = 0; e < NE; ++e) nz |= (x[e] > LCCRF_NEG_INF) ? (Mask(1) << e) : Mask(0);
             return nz;
         };
-        unsigned nz = 0;
+        Mask nz = 0;
         bool hole;
         if constexpr (Src::kPaddingIsFinite) {
             hole = src.smallest_loaded(ring[slot]) == LCCRF_NEG_INF;
@@ -315,29 +413,29 @@ __device__ __forceinline__ bool linear_product(const Src& src, int first, int la
 #pragma unroll
                 for (int sb = 0; sb < NB; ++sb)
 #pragma unroll
-                    for (int rb = 0; rb < NB; ++rb)
+                    for (int rl = 0; rl < RB; ++rl)
 #pragma unroll
-                        for (int v = 0; v < 4; ++v) Z[sb][rb][v] = (in >> ((sb * NB + rb) * 4 + v)) & 1 ? 1.f : 0.f;
+                        for (int v = 0; v < 4; ++v) Z[sb][rl][v] = inside(sb, rl, v) ? 1.f : 0.f;
             }
         }
         started = true;
         // Exponent fields of the new entries: their largest gives each column's rescale, the
         // smallest among the entries that some path reaches says whether the product still holds.
-        unsigned fld[NB][NB][4], fmin = L::kNoField;
+        unsigned fld[NB][RB][4], fmin = L::kNoField;
 #pragma unroll
         for (int tb = 0; tb < NB; ++tb)
 #pragma unroll
-            for (int rb = 0; rb < NB; ++rb)
+            for (int rl = 0; rl < RB; ++rl)
 #pragma unroll
-                for (int v = 0; v < 4; ++v) fld[tb][rb][v] = L::field(acc[tb][rb][v]);
+                for (int v = 0; v < 4; ++v) fld[tb][rl][v] = L::field(acc[tb][rl][v]);
         if (tracking) {
             if constexpr (Src::kPaddingIsFinite) nz = nonzero_mask();
-            const unsigned nzp = (unsigned)__shfl((int)nz, pj, 64);
-            f32x4 pat[NB][NB];
+            const Mask nzp = shfl_mask(nz, pj);
+            f32x4 pat[NB][RB];
 #pragma unroll
             for (int tb = 0; tb < NB; ++tb)
 #pragma unroll
-                for (int rb = 0; rb < NB; ++rb) pat[tb][rb] = f32x4{0.f, 0.f, 0.f, 0.f};
+                for (int rl = 0; rl < RB; ++rl) pat[tb][rl] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
             for (int sb = 0; sb < NB; ++sb)
 #pragma unroll
@@ -346,27 +444,26 @@ __device__ __forceinline__ bool linear_product(const Src& src, int first, int la
                     for (int v = 0; v < 4; ++v) {
                         const float flag = (nzp >> ((sb * NB + tb) * 4 + v)) & 1 ? 1.f : 0.f;
 #pragma unroll
-                        for (int rb = 0; rb < NB; ++rb)
-                            pat[tb][rb] = __builtin_amdgcn_mfma_f32_16x16x4f32(flag, Z[sb][rb][v], pat[tb][rb], 0, 0, 0);
+                        for (int rl = 0; rl < RB; ++rl)
+                            pat[tb][rl] = __builtin_amdgcn_mfma_f32_16x16x4f32(flag, Z[sb][rl][v], pat[tb][rl], 0, 0, 0);
                     }
 #pragma unroll
             for (int tb = 0; tb < NB; ++tb)
 #pragma unroll
-                for (int rb = 0; rb < NB; ++rb)
+                for (int rl = 0; rl < RB; ++rl)
 #pragma unroll
                     for (int v = 0; v < 4; ++v) {
-                        const bool reached = pat[tb][rb][v] > 0.f;
-                        Z[tb][rb][v] = reached ? 1.f : 0.f;
-                        fmin = min(fmin, reached ? fld[tb][rb][v] : L::kNoField);
+                        const bool reached = pat[tb][rl][v] > 0.f;
+                        Z[tb][rl][v] = reached ? 1.f : 0.f;
+                        fmin = min(fmin, reached ? fld[tb][rl][v] : L::kNoField);
                     }
         } else {
 #pragma unroll
             for (int tb = 0; tb < NB; ++tb)
 #pragma unroll
-                for (int rb = 0; rb < NB; ++rb)
+                for (int rl = 0; rl < RB; ++rl)
 #pragma unroll
-                    for (int v = 0; v < 4; ++v)
-                        fmin = min(fmin, (in >> ((tb * NB + rb) * 4 + v)) & 1 ? fld[tb][rb][v] : L::kNoField);
+                    for (int v = 0; v < 4; ++v) fmin = min(fmin, inside(tb, rl, v) ? fld[tb][rl][v] : L::kNoField);
         }
         bad |= fmin < L::kMinField;  // also zero and subnormal entries (field 0)
         if (!F64 && __builtin_amdgcn_ballot_w64(bad) != 0) {
@@ -377,127 +474,146 @@ __device__ __forceinline__ bool linear_product(const Src& src, int first, int la
         // below the smallest normal number: it cannot matter to a sum of the accepted size.
         // Power-of-two rescale of each entry tag's column (exact): the largest exponent.
 #pragma unroll
-        for (int rb = 0; rb < NB; ++rb) {
+        for (int rl = 0; rl < RB; ++rl) {
             unsigned ef = 0;
 #pragma unroll
             for (int tb = 0; tb < NB; ++tb)
 #pragma unroll
-                for (int v = 0; v < 4; ++v) ef = max(ef, fld[tb][rb][v]);
+                for (int v = 0; v < 4; ++v) ef = max(ef, fld[tb][rl][v]);
             const auto r16 = __builtin_amdgcn_permlane16_swap(ef, ef, false, false);
             ef = max(r16[0], r16[1]);
             const auto r32 = __builtin_amdgcn_permlane32_swap(ef, ef, false, false);
             ef = max(r32[0], r32[1]);
             const int ex = ef > 0 ? (int)ef - (int)L::kBias : 0;  // a column without any path keeps its zeros
-            esum[rb] += ex;
+            esum[rl] += ex;
 #pragma unroll
             for (int tb = 0; tb < NB; ++tb)
 #pragma unroll
-                for (int v = 0; v < 4; ++v) D[tb][rb][v] = L::scaled(acc[tb][rb][v], ex);
+                for (int v = 0; v < 4; ++v) D[tb][rl][v] = L::scaled(acc[tb][rl][v], ex);
         }
         return true;
     };
     if constexpr (F64) walk<Src::PF>(first, last, +1, load, step);
     else walk_while<Src::PF>(first, last, +1, load, step);
     rejected |= __builtin_amdgcn_ballot_w64(bad) != 0;
-    if (!rejected) {
-        float ef[NB], emax = LCCRF_NEG_INF;
+    float ef[RB], emax = LCCRF_NEG_INF;
 #pragma unroll
-        for (int rb = 0; rb < NB; ++rb) {
-            ef[rb] = 16 * rb + j < T ? (float)esum[rb] : LCCRF_NEG_INF;
-            emax = fmaxf(emax, xor_max<1, 16>(ef[rb]));
+    for (int rl = 0; rl < RB; ++rl) {
+        ef[rl] = S::tag(rb0 + rl, j) < T ? (float)esum[rl] : LCCRF_NEG_INF;
+        emax = fmaxf(emax, xor_max<1, 16>(ef[rl]));
+    }
+    if constexpr (S::NW > 1) {
+        // the waves of the workgroup agree on the verdict and on the largest column scale (a wave that gave up
+        // early waits here for the others)
+        if (lane == 0) {
+            shared.emax[F64][wv] = emax;
+            shared.rejected[F64][wv] = rejected ? 1 : 0;
         }
+        __syncthreads();
+#pragma unroll
+        for (int w = 0; w < S::NW; ++w) {
+            emax = fmaxf(emax, shared.emax[F64][w]);
+            rejected |= shared.rejected[F64][w] != 0;
+        }
+    }
+    if (!rejected) {
         emax = finite_or_zero(emax);
 #pragma unroll
         for (int tb = 0; tb < NB; ++tb)
 #pragma unroll
-            for (int rb = 0; rb < NB; ++rb)
+            for (int rl = 0; rl < RB; ++rl)
 #pragma unroll
-                for (int v = 0; v < 4; ++v) {
-                    const bool inside = (in >> ((tb * NB + rb) * 4 + v)) & 1;
-                    Pout[S::row(lane, (tb * NB + rb) * 4 + v) * TP + 16 * rb + j] =
-                        (inside && D[tb][rb][v] > 0) ? L::log2_of(D[tb][rb][v]) : LCCRF_NEG_INF;
-                }
+                for (int v = 0; v < 4; ++v)
+                    Pout[S::row(lane, (tb * NB + rb0 + rl) * 4 + v) * TP + S::tag(rb0 + rl, j)] =
+                        (inside(tb, rl, v) && D[tb][rl][v] > 0) ? L::log2_of(D[tb][rl][v]) : LCCRF_NEG_INF;
         if (g == 0) {
 #pragma unroll
-            for (int rb = 0; rb < NB; ++rb) rel_out[16 * rb + j] = ef[rb] - emax;
+            for (int rl = 0; rl < RB; ++rl) rel_out[S::tag(rb0 + rl, j)] = ef[rl] - emax;
         }
-        if (lane == 0) *base_out = Msum + (double)emax;
+        if (threadIdx.x == 0) *base_out = Msum + (double)emax;
         return true;
     }
     return false;
 }
 
 // The same product in the log domain, every log-sum-exp shifted by its own maximum (rare: taken when
-// both linear products gave up).  Lane (r = lane / LPRow, q = lane % LPRow) owns
-// P[r][CPL q .. CPL q + CPL - 1]; P and the current matrix are exchanged through LDS.
+// both linear products gave up), by all threads of the workgroup.  Thread (r = tid / XL, q = tid % XL)
+// owns P[r][XC q .. XC q + XC - 1]; P and the current matrix are exchanged through LDS.
 template <int TP, typename Src>
 __device__ __forceinline__ void exact_product(const Src& src, int first, int last, int T, float* __restrict__ Pout,
                                               float* __restrict__ rel_out, double* __restrict__ base_out,
                                               float (*Pc)[TP + 1], float (*Ph)[TP + 1]) {
     using S = ScanShape<TP, true>;
-    const int lane = threadIdx.x;
-    constexpr int LPRow = S::LPRow, CPL = S::CPL;
-    const int r = lane / LPRow, q = lane % LPRow;
-    float out[CPL];
+    const int tid = threadIdx.x;
+    constexpr int XL = S::XL, XC = S::XC;
+    const int r = tid / XL, q = tid % XL;
+    float out[XC];
 #pragma unroll
-    for (int jj = 0; jj < CPL; ++jj) out[jj] = (r == CPL * q + jj) ? 0.f : LCCRF_NEG_INF;
+    for (int jj = 0; jj < XC; ++jj) out[jj] = (r == XC * q + jj) ? 0.f : LCCRF_NEG_INF;
     float sg = 0.f;  // integer valued
     double osum = 0.0;
     for (int i = first; i <= last; ++i) {
         osum += src.offset(i);
         __syncthreads();
 #pragma unroll
-        for (int jj = 0; jj < CPL; ++jj) {
-            const int t = CPL * q + jj;
+        for (int jj = 0; jj < XC; ++jj) {
+            const int t = XC * q + jj;
             Pc[r][t] = out[jj];
             Ph[r][t] = src.entry(i, r, t);
         }
         __syncthreads();
-        float mx[CPL], sm[CPL];
+        float mx[XC], sm[XC];
 #pragma unroll
-        for (int jj = 0; jj < CPL; ++jj) {
+        for (int jj = 0; jj < XC; ++jj) {
             mx[jj] = LCCRF_NEG_INF;
             sm[jj] = 0.f;
         }
         for (int s = 0; s < TP; ++s) {
             const float p = Pc[r][s];
 #pragma unroll
-            for (int jj = 0; jj < CPL; ++jj) mx[jj] = fmaxf(mx[jj], p + Ph[s][CPL * q + jj]);
+            for (int jj = 0; jj < XC; ++jj) mx[jj] = fmaxf(mx[jj], p + Ph[s][XC * q + jj]);
         }
         for (int s = 0; s < TP; ++s) {
             const float p = Pc[r][s];
 #pragma unroll
-            for (int jj = 0; jj < CPL; ++jj) sm[jj] += ex2(p + Ph[s][CPL * q + jj] - finite_or_zero(mx[jj]));
+            for (int jj = 0; jj < XC; ++jj) sm[jj] += ex2(p + Ph[s][XC * q + jj] - finite_or_zero(mx[jj]));
         }
         float rm = LCCRF_NEG_INF;
 #pragma unroll
-        for (int jj = 0; jj < CPL; ++jj) {
+        for (int jj = 0; jj < XC; ++jj) {
             out[jj] = mx[jj] + lg2(sm[jj]);
             rm = fmaxf(rm, out[jj]);
         }
         // shift the row by the integer part of its maximum: scales stay integers, hence exact
-        rm = xor_max<1, LPRow>(rm);
+        rm = xor_max<1, XL>(rm);
         const float sh = floorf(finite_or_zero(rm));
         sg += sh;
 #pragma unroll
-        for (int jj = 0; jj < CPL; ++jj) out[jj] -= sh;
+        for (int jj = 0; jj < XC; ++jj) out[jj] -= sh;
     }
     const float ef = r < T ? sg : LCCRF_NEG_INF;
-    const float emax = finite_or_zero(xor_max<LPRow, 64>(ef));
+    // the largest row scale, over all rows of the workgroup: through LDS
+    __syncthreads();
+    if (q == 0) Pc[0][r] = ef;
+    __syncthreads();
+    float emax = LCCRF_NEG_INF;
+    for (int k = 0; k < TP; ++k) emax = fmaxf(emax, Pc[0][k]);
+    emax = finite_or_zero(emax);
 #pragma unroll
-    for (int jj = 0; jj < CPL; ++jj) {
-        const int t = CPL * q + jj;
+    for (int jj = 0; jj < XC; ++jj) {
+        const int t = XC * q + jj;
         Pout[t * TP + r] = (r < T && t < T) ? out[jj] : LCCRF_NEG_INF;
     }
     if (q == 0) rel_out[r] = ef - emax;
-    if (lane == 0) *base_out = osum + (double)emax;
+    if (tid == 0) *base_out = osum + (double)emax;
 }
 
-// One wave per chunk: the product of the chunk's potentials.
-template <typename TIN, int TP>
-__global__ __launch_bounds__(64) void chunk_product_kernel(ScanArgs a) {
+// One wave (up to 32 tags) or NB waves per chunk: the product of the chunk's potentials.
+template <typename TIN, int TP, bool VEC>
+__global__ __launch_bounds__(64 * ScanShape<TP>::NW) void chunk_product_kernel(ScanArgs a) {
     __shared__ float Pc[TP][TP + 1];
     __shared__ float Ph[TP][TP + 1];
+    __shared__ ProductShared shared;
     const int b = blockIdx.x / a.C, c = blockIdx.x % a.C;
     const int T = a.T, N = a.N;
     const int L = clamp_length(a.lengths, b, N);
@@ -508,20 +624,22 @@ __global__ __launch_bounds__(64) void chunk_product_kernel(ScanArgs a) {
     const size_t bc = (size_t)b * a.C + c;
     float* Pout = a.Pl + bc * TP * TP;
     float* rel_out = a.rel + bc * TP;
+    const int lane = threadIdx.x & 63;
     if constexpr (kSingleFirst<TP>) {
-        const PotentialMatrices<TIN, TP, false> src(phib, T, threadIdx.x);
-        if (linear_product<TP, false>(src, first, last, T, Pout, rel_out, a.base + bc)) return;
+        const PotentialMatrices<TIN, TP, false, VEC> src(phib, T, lane);
+        if (linear_product<TP, false>(src, first, last, T, Pout, rel_out, a.base + bc, shared)) return;
     }
-    const PotentialMatrices<TIN, TP, true> src(phib, T, threadIdx.x);
-    if (linear_product<TP, true>(src, first, last, T, Pout, rel_out, a.base + bc)) return;
+    const PotentialMatrices<TIN, TP, true, VEC> src(phib, T, lane);
+    if (linear_product<TP, true>(src, first, last, T, Pout, rel_out, a.base + bc, shared)) return;
     exact_product<TP>(src, first, last, T, Pout, rel_out, a.base + bc, Pc, Ph);
 }
 
-// One wave per group of GS chunks: the product of the group's chunk products.
+// One wave (or NB waves) per group of GS chunks: the product of the group's chunk products.
 template <int TP>
-__global__ __launch_bounds__(64) void group_product_kernel(ScanArgs a) {
+__global__ __launch_bounds__(64 * ScanShape<TP>::NW) void group_product_kernel(ScanArgs a) {
     __shared__ float Pc[TP][TP + 1];
     __shared__ float Ph[TP][TP + 1];
+    __shared__ ProductShared shared;
     const int b = blockIdx.x / a.G, g = blockIdx.x % a.G;
     const int L = clamp_length(a.lengths, b, a.N);
     const int Cb = (L + a.chunk - 1) / a.chunk;  // chunks of this sequence
@@ -531,12 +649,13 @@ __global__ __launch_bounds__(64) void group_product_kernel(ScanArgs a) {
     const size_t cb = (size_t)b * a.C, bg = (size_t)b * a.G + g;
     float* Pout = a.Pl2 + bg * TP * TP;
     float* rel_out = a.rel2 + bg * TP;
+    const int lane = threadIdx.x & 63;
     if constexpr (kSingleFirst<TP>) {
-        const ChunkMatrices<TP, false> src(a.Pl + cb * TP * TP, a.rel + cb * TP, a.base + cb, a.T, threadIdx.x);
-        if (linear_product<TP, false>(src, c0, c1, a.T, Pout, rel_out, a.base2 + bg)) return;
+        const ChunkMatrices<TP, false> src(a.Pl + cb * TP * TP, a.rel + cb * TP, a.base + cb, a.T, lane);
+        if (linear_product<TP, false>(src, c0, c1, a.T, Pout, rel_out, a.base2 + bg, shared)) return;
     }
-    const ChunkMatrices<TP, true> src(a.Pl + cb * TP * TP, a.rel + cb * TP, a.base + cb, a.T, threadIdx.x);
-    if (linear_product<TP, true>(src, c0, c1, a.T, Pout, rel_out, a.base2 + bg)) return;
+    const ChunkMatrices<TP, true> src(a.Pl + cb * TP * TP, a.rel + cb * TP, a.base + cb, a.T, lane);
+    if (linear_product<TP, true>(src, c0, c1, a.T, Pout, rel_out, a.base2 + bg, shared)) return;
     exact_product<TP>(src, c0, c1, a.T, Pout, rel_out, a.base2 + bg, Pc, Ph);
 }
 
@@ -553,8 +672,9 @@ __global__ __launch_bounds__(64) void group_product_kernel(ScanArgs a) {
 template <typename TIN, int TP>
 __global__ __launch_bounds__(64) void chunk_boundary_kernel(ScanArgs a) {
     using S = ScanShape<TP, true>;
-    constexpr int LPRow = S::LPRow, CPL = S::CPL, PF = TP == 16 ? kScanPF : 4;
+    constexpr int LPRow = S::LPRow, CPL = S::CPL, PF = TP == 16 ? kScanPF : TP == 32 ? 4 : 2;
     const int lane = threadIdx.x, o = lane / LPRow, q = lane % LPRow;
+    const int oc = o < TP ? o : TP - 1;  // (48 tags: the last 16 lanes have no entry; they load what lane 47 loads)
     const int dir = blockIdx.x & 1;
     const int unit = blockIdx.x >> 1;
     const bool grouped = a.GS > 0;
@@ -601,7 +721,7 @@ __global__ __launch_bounds__(64) void chunk_boundary_kernel(ScanArgs a) {
         float pm[PF][CPL], rl[PF][CPL];
         double bs[PF];
         auto load = [&](int c, int slot) {
-            const float* P = a.Pl + (cb + c) * TP * TP + o * TP + CPL * q;
+            const float* P = a.Pl + (cb + c) * TP * TP + oc * TP + CPL * q;
             const float* E = a.rel + (cb + c) * TP + CPL * q;
 #pragma unroll
             for (int k = 0; k < CPL; k += 4) {
@@ -619,7 +739,7 @@ __global__ __launch_bounds__(64) void chunk_boundary_kernel(ScanArgs a) {
             for (int jj = 0; jj < CPL; ++jj) x[jj] = lane_bperm(nv, LPRow * (CPL * q + jj)) + (pm[slot][jj] + rl[slot][jj]);
             const float r = lse(x);
             O += bs[slot] + (double)dprev;
-            nv = r - dprev;
+            nv = o < TP ? r - dprev : LCCRF_NEG_INF;  // (lanes past the padded tag count hold no entry)
             dprev = finite_or_zero(xor_max<LPRow, 64>(nv));  // used by the next step
             if (q == 0 && o < T) a.Fv[(cb + c) * T + o] = nv;
             if (lane == 0) a.OF[cb + c] = O;
@@ -645,8 +765,8 @@ __global__ __launch_bounds__(64) void chunk_boundary_kernel(ScanArgs a) {
         auto load = [&](int c, int slot) {
             const float* P = a.Pl + (cb + c) * TP * TP;
 #pragma unroll
-            for (int jj = 0; jj < CPL; ++jj) pm[slot][jj] = P[(CPL * q + jj) * TP + o];
-            rl[slot] = a.rel[(cb + c) * TP + o];
+            for (int jj = 0; jj < CPL; ++jj) pm[slot][jj] = P[(CPL * q + jj) * TP + oc];
+            rl[slot] = a.rel[(cb + c) * TP + oc];
             bs[slot] = a.base[cb + c];
         };
         // chunk c takes beta at its last position to beta at the last position of chunk c - 1
@@ -656,7 +776,7 @@ __global__ __launch_bounds__(64) void chunk_boundary_kernel(ScanArgs a) {
             for (int jj = 0; jj < CPL; ++jj) x[jj] = pm[slot][jj] + lane_bperm(nv, LPRow * (CPL * q + jj));
             const float r = lse(x) + rl[slot];
             O += bs[slot] + (double)dprev;
-            nv = r - dprev;
+            nv = o < TP ? r - dprev : LCCRF_NEG_INF;  // (lanes past the padded tag count hold no entry)
             dprev = finite_or_zero(xor_max<LPRow, 64>(nv));
             if (q == 0 && o < T) a.Gv[(cb + c - 1) * T + o] = nv;
             if (lane == 0) a.OG[cb + c - 1] = O;
@@ -901,10 +1021,10 @@ __global__ __launch_bounds__(64) void chunk_maxplus_boundary_kernel(MaxScanArgs 
 }
 
 // ---------------------------------------------------------------------------------------
-// Sum queries: tag sets up to 32 (matrices in one or four 16 x 16 blocks); the max-plus scan: up to 16.
-bool scan_supported(int T) { return T >= 1 && T <= 32; }
+// Sum queries: tag sets up to 64 (matrices in 1, 4, 9 or 16 blocks of 16 x 16); the max-plus scan: up to 16.
+bool scan_supported(int T) { return T >= 1 && T <= 64; }
 bool scan_supported_max(int T) { return T >= 1 && T <= 16; }
-int scan_padded_tags(int T) { return T <= 16 ? 16 : 32; }
+int scan_padded_tags(int T) { return (T + 15) / 16 * 16; }
 
 // Chunks per group when phase B is itself run as a scan; 0: one serial pass over all chunks.  The
 // group products cost about 3.5 times a vector step each and two serial stages follow them
@@ -918,7 +1038,14 @@ int scan_group_size(int C) {
 
 template <typename TIN, int TP>
 static hipError_t launch_scan_boundaries_t(ScanArgs a, const ScanGroupBuffers& gb, hipStream_t st) {
-    hipLaunchKernelGGL((chunk_product_kernel<TIN, TP>), dim3(a.B * a.C), dim3(64), 0, st, a);
+    constexpr int kProductThreads = 64 * ScanShape<TP>::NW;
+    // vector loads of a lane's NB neighbouring columns: T a multiple of NB, and the rows aligned for them
+    constexpr int NB = ScanShape<TP>::NB;
+    const bool vec = NB > 1 && a.T % NB == 0 && (NB == 3 ? sizeof(TIN) == 4 : true);
+    if (vec)
+        hipLaunchKernelGGL((chunk_product_kernel<TIN, TP, true>), dim3(a.B * a.C), dim3(kProductThreads), 0, st, a);
+    else
+        hipLaunchKernelGGL((chunk_product_kernel<TIN, TP, false>), dim3(a.B * a.C), dim3(kProductThreads), 0, st, a);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     const int gs = scan_group_size(a.C);
@@ -930,7 +1057,7 @@ static hipError_t launch_scan_boundaries_t(ScanArgs a, const ScanGroupBuffers& g
     // products of the groups
     ScanArgs p = a;
     p.GS = gs; p.G = G; p.Pl2 = gb.Pl2; p.rel2 = gb.rel2; p.base2 = gb.base2;
-    hipLaunchKernelGGL(group_product_kernel<TP>, dim3(a.B * G), dim3(64), 0, st, p);
+    hipLaunchKernelGGL(group_product_kernel<TP>, dim3(a.B * G), dim3(kProductThreads), 0, st, p);
     if ((e = hipGetLastError()) != hipSuccess) return e;
     // phase B over the groups: the same kernel, a group in the place of a chunk (this launch writes logZ)
     ScanArgs u = a;
@@ -955,7 +1082,13 @@ hipError_t launch_scan_boundaries(int dtype, const void* phi, const int32_t* len
                0, 1, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr};
     if (T <= 16)
         return dtype == 0 ? launch_scan_boundaries_t<float, 16>(a, gb, st) : launch_scan_boundaries_t<uint16_t, 16>(a, gb, st);
-    return dtype == 0 ? launch_scan_boundaries_t<float, 32>(a, gb, st) : launch_scan_boundaries_t<uint16_t, 32>(a, gb, st);
+    if (T <= 32)
+        return dtype == 0 ? launch_scan_boundaries_t<float, 32>(a, gb, st) : launch_scan_boundaries_t<uint16_t, 32>(a, gb, st);
+    if (T <= 48)
+        return dtype == 0 ? launch_scan_boundaries_t<float, 48>(a, gb, st) : launch_scan_boundaries_t<uint16_t, 48>(a, gb, st);
+    if (T <= 64)
+        return dtype == 0 ? launch_scan_boundaries_t<float, 64>(a, gb, st) : launch_scan_boundaries_t<uint16_t, 64>(a, gb, st);
+    return hipErrorInvalidValue;
 }
 
 

@@ -71,6 +71,10 @@ def test_auto_schedule_is_reported_without_a_gpu(lib):
     assert binding.auto_algo(binding.OP_ARGMAX, 256, 256, 16) == binding.ALGO_SEQUENTIAL
     assert binding.auto_algo(binding.OP_MARGINALS, 256, 256, 16) == binding.ALGO_SCAN
     assert binding.auto_algo(binding.OP_MARGINALS, 4, 8, 5) == binding.ALGO_SEQUENTIAL       # config 1
+    assert binding.auto_algo(binding.OP_MARGINALS, 128, 128, 48) == binding.ALGO_SEQUENTIAL  # config 3: too many positions
+    assert binding.auto_algo(binding.OP_MARGINALS, 32, 256, 48) == binding.ALGO_SCAN         # 33 .. 64 tags, small batch
+    assert binding.auto_algo(binding.OP_ENTROPY, 32, 256, 48) == binding.ALGO_SEQUENTIAL     # entropy by edges: 32 tags at most
+    assert binding.auto_algo(binding.OP_SAMPLE, 32, 256, 48) == binding.ALGO_SEQUENTIAL
     with pytest.raises(binding.LccrfError):
         binding.auto_algo(binding.OP_MARGINALS, 1, 8, 0)
     with pytest.raises(binding.LccrfError):

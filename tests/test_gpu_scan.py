@@ -203,8 +203,74 @@ def test_scan_32_tags_agrees_with_sequential_on_the_paper_shape(crf):
     assert float((mu_a - mu_b).abs().max()) < 5e-6
 
 
+@pytest.mark.parametrize("k", [4, 7, 32])
+@pytest.mark.parametrize("T,N", [(33, 9), (40, 65), (48, 1), (48, 130), (49, 40), (64, 3), (64, 64), (64, 150), (57, 90)])
+def test_scan_up_to_64_tags(crf, oracle_mod, chunk, T, N, k):
+    """Tag sets of 33 .. 64: chunk products in 3 x 3 or 4 x 4 blocks of 16 x 16, one wave per block column of
+    the running product; the chunks themselves by the four-wave chain kernels."""
+    chunk(k)
+    lens = _lens_around_chunks(N, k)
+    phi, _ = workloads.random_case(6900 + 31 * T + N, len(lens), N, T, scale=1.5)
+    check_case(crf, oracle_mod, phi, lens, algo=crf.ALGO_SCAN, what=f"scan T={T} N={N} k={k}", queries=SUMS)
+
+
+@pytest.mark.parametrize("T", [48, 64])
+def test_scan_64_tags_bf16_forbidden_edges_jumps_and_offsets(crf, oracle_mod, chunk, T):
+    chunk(16)
+    N = 200
+    phi, lens = workloads.random_case(6910 + T, 5, N, T, scale=3.0, ragged=True, min_len=3, dtype="bf16")
+    check_case(crf, oracle_mod, phi, lens, poison=False, algo=crf.ALGO_SCAN, what=f"scan T={T} bf16", queries=SUMS)
+    chunk(8)
+    N = 50
+    phi, _ = workloads.random_case(6920 + T, 5, N, T - 3)
+    ninf = float("-inf")
+    phi[0, :, 3, :] = ninf
+    phi[1, 20, :, 27] = ninf
+    phi[2, 30, :, :] = ninf
+    mask = torch.rand(N, T - 3, T - 3, generator=torch.Generator().manual_seed(5)) < 0.6
+    phi[3][mask] = ninf
+    phi[3, :, torch.arange(T - 3), torch.arange(T - 3)] = 0.0
+    lens = torch.tensor([50, 50, 50, 50, 33], dtype=torch.int32)
+    check_case(crf, oracle_mod, phi, lens, poison=False, algo=crf.ALGO_SCAN, what=f"scan T={T - 3} -inf", queries=SUMS)
+    N = 70
+    phi, lens = workloads.random_case(6930 + T, 4, N, T, scale=1.0, ragged=True, min_len=N // 2)
+    g = torch.Generator().manual_seed(17)
+    jump = (torch.randint(0, 3, (4, N, 1, 1), generator=g).to(torch.float32) - 1.0) * 300.0
+    wide = torch.randint(0, 2, (4, N, T, T), generator=g).to(torch.float32) * -150.0
+    wide[:, ::3] = 0.0
+    check_case(crf, oracle_mod, (phi + jump + wide).contiguous(), lens, algo=crf.ALGO_SCAN, what=f"scan T={T} jumps",
+               queries=SUMS)
+    chunk(16)
+    phi, lens = workloads.random_case(6940 + T, 3, 120, T - 7, scale=1.0, ragged=True, min_len=60)
+    check_case(crf, oracle_mod, (phi + 40.0).contiguous(), lens, algo=crf.ALGO_SCAN, what=f"scan T={T - 7} offsets",
+               queries=SUMS)
+
+
+@pytest.mark.parametrize("scale", [5.0, 8.0, 10.0])
+@pytest.mark.parametrize("T", [41, 64])
+def test_scan_64_tags_precision_ladder(crf, oracle_mod, chunk, T, scale):
+    """Single precision first, double precision where its exponent range runs out, with group products
+    above the chunk products (many chunks).  Scales up to 10, the peaked case of the long-chain workload
+    (float32 potentials of scale 12 over 64 tags bring every schedule, the exact sequential one included,
+    to 7e-6 .. 1e-5 of the oracle: the rounding of arguments of magnitude 60 in float32)."""
+    chunk(16)
+    phi, lens = workloads.random_case(6950 + T, 2, 1100, T, scale=scale, ragged=True, min_len=900)
+    check_case(crf, oracle_mod, phi, lens, algo=crf.ALGO_SCAN, what=f"scan T={T} scale {scale}", queries=SUMS)
+
+
+def test_scan_config3_agrees_with_sequential(crf):
+    w = workloads.WORKLOADS["cfg3"]
+    dphi, dl = workloads.phi_batch(w).cuda(), workloads.lengths(w).cuda()
+    lz_a, mu_a = crf.lccrf_marginals(dphi, dl, algo=crf.ALGO_SCAN)
+    lz_b, mu_b = crf.lccrf_marginals(dphi, dl, algo=crf.ALGO_SEQUENTIAL)
+    lz_c = crf.lccrf_log_partition(dphi, dl, algo=crf.ALGO_SCAN)
+    assert torch.allclose(lz_a, lz_b, rtol=2e-6, atol=0)
+    assert torch.allclose(lz_c, lz_b, rtol=2e-6, atol=0)
+    assert float((mu_a - mu_b).abs().max()) < 5e-6
+
+
 def test_scan_needs_a_small_tag_set(crf):
-    phi, _ = workloads.random_case(5800, 2, 8, 33)
+    phi, _ = workloads.random_case(5800, 2, 8, 65)
     with pytest.raises(crf.LccrfError, match="not available"):
         crf.lccrf_marginals(phi.cuda(), None, algo=crf.ALGO_SCAN)
     phi, _ = workloads.random_case(5801, 2, 8, 17)
