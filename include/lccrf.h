@@ -241,6 +241,20 @@ int lccrf_sample(const void* phi, lccrf_dtype dt, const int32_t* lengths, const 
                  void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * lccrf_sample with the randomness drawn inside the library from an explicit key, as the paper asks of
+ * sampling (section "Sampling a Structure": reproducible samples from explicit random keys): the uniform of
+ * position i of sequence b is produced by the counter-based generator Philox4x32-10 (Salmon, Moraes, Dror
+ * and Shaw, 2011: multipliers 0xD2511F53 and 0xCD9E8D57, key increments 0x9E3779B9 and 0xBB67AE85, ten
+ * rounds) with key (seed mod 2^32, seed / 2^32) and counter (k mod 2^32, k / 2^32, 0, 0), k = b * N + i: the
+ * upper 24 bits of the first output word times 2^-24.  Every draw depends on (seed, b, i) alone; the same
+ * seed gives the same tags on every call, and lccrf_sample fed those uniforms gives the same tags too.
+ * Other arguments, outputs, workspace and errors as lccrf_sample.
+ */
+int lccrf_sample_seeded(const void* phi, lccrf_dtype dt, const int32_t* lengths, uint64_t seed,
+                        int B, int N, int T, int32_t* tags,
+                        void* workspace, size_t workspace_bytes, void* stream);
+
+/*
  * Semi-Markov CRF, log-partition (paper, section "Segmentation with Semi-Markov CRF": the linear
  * chain's parametrisation with transition matrices, except that a transition may jump over
  * several positions; forward algorithm in O(K T^2 N)).  A structure splits positions 0..L-1 into
@@ -266,7 +280,7 @@ int lccrf_semi_markov_log_partition(const void* phi, lccrf_dtype dt, const int32
  * (marginals still write the dense [B,N,T,T] result).  Results equal those of the dense calls on
  * the materialised phi up to rounding; the first tag is scored trans[0][t] + emit[b][0][t].
  *   emit   [B][N][T] float32 (device), 16-byte aligned; trans [T][T] float32 (device), 16-byte aligned.
- * T <= 64 (else LCCRF_ENOTIMPL).  Workspace: lccrf_workspace_bytes of the matching op with LCCRF_F32.
+ * T <= 128 (else LCCRF_ENOTIMPL).  Workspace: lccrf_workspace_bytes of the matching op with LCCRF_F32.
  * Other arguments, outputs and errors as the dense calls.
  */
 int lccrf_log_partition_structured(const float* emit, const float* trans, const int32_t* lengths,

@@ -34,7 +34,7 @@ EXPORTS = (
     "lccrf_sample", "lccrf_semi_markov_log_partition", "lccrf_log_partition_structured",
     "lccrf_marginals_structured", "lccrf_argmax_structured", "lccrf_set_scan_chunk", "lccrf_auto_algo",
     "lccrf_strerror", "lccrf_version", "lccrf_marginals_static", "lccrf_static_scratch_bytes",
-    "lccrf_set_pair_poll_limit", "lccrf_stream_probe", "lccrf_stream_probe_bytes",
+    "lccrf_set_pair_poll_limit", "lccrf_stream_probe", "lccrf_stream_probe_bytes", "lccrf_sample_seeded",
 )
 
 _lib = None
@@ -82,6 +82,8 @@ def load_library() -> ctypes.CDLL:
     lib.lccrf_semi_markov_log_partition.restype = i
     lib.lccrf_sample.argtypes = [vp, i, vp, vp, i, i, i, vp, vp, sz, vp]
     lib.lccrf_sample.restype = i
+    lib.lccrf_sample_seeded.argtypes = [vp, i, vp, ctypes.c_uint64, i, i, i, vp, vp, sz, vp]
+    lib.lccrf_sample_seeded.restype = i
     sbase = [vp, vp, vp, i, i, i]
     lib.lccrf_log_partition_structured.argtypes = sbase + [vp, vp, sz, vp]
     lib.lccrf_marginals_structured.argtypes = sbase + [vp, vp, vp, sz, vp]
@@ -323,6 +325,22 @@ def lccrf_sample(phi: torch.Tensor, uniforms: torch.Tensor, lengths: Optional[to
         rc = lib.lccrf_sample(phi.data_ptr(), dt, _len_ptr(lengths, B, phi.device), uniforms.data_ptr(), B, N, T,
                               out.data_ptr(), ws.data_ptr(), nws, _stream(phi.device))
     _check(rc, "lccrf_sample")
+    return out
+
+
+def lccrf_sample_seeded(phi: torch.Tensor, seed: int, lengths: Optional[torch.Tensor] = None, *,
+                        out: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """One sampled tag path per sequence [B, N] int32 (-1 past the length) with the uniforms drawn in the library by
+    Philox4x32-10 under the 64-bit `seed` (counter b * N + i): reproducible from the seed alone."""
+    lib = load_library()
+    dt, B, N, T = _phi_args(phi)
+    ws, nws = _workspace(OP_SAMPLE, B, N, T, dt, phi.device, workspace)
+    if out is None:
+        out = torch.empty(B, N, dtype=torch.int32, device=phi.device)
+    with torch.cuda.device(phi.device):
+        rc = lib.lccrf_sample_seeded(phi.data_ptr(), dt, _len_ptr(lengths, B, phi.device), int(seed) & (2 ** 64 - 1), B, N, T,
+                                     out.data_ptr(), ws.data_ptr(), nws, _stream(phi.device))
+    _check(rc, "lccrf_sample_seeded")
     return out
 
 

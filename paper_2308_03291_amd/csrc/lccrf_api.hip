@@ -529,14 +529,15 @@ int lccrf_semi_markov_log_partition(const void* phi, lccrf_dtype dt, const int32
     return e == hipSuccess ? LCCRF_OK : LCCRF_ELAUNCH;
 }
 
-int lccrf_sample(const void* phi, lccrf_dtype dt, const int32_t* lengths, const float* uniforms, int B, int N, int T,
-                 int32_t* tags, void* workspace, size_t workspace_bytes, void* stream) {
+static int sample_query(const void* phi, lccrf_dtype dt, const int32_t* lengths, const float* uniforms, bool seeded,
+                        unsigned long long seed, int B, int N, int T, int32_t* tags, void* workspace, size_t workspace_bytes,
+                        void* stream) {
     const KnobSnapshot knobs;
     const size_t need = lccrf_workspace_bytes(LCCRF_OP_SAMPLE, B, N, T, dt);
     const int rc = check_common(phi, dt, B, N, T, workspace, workspace_bytes, need, LCCRF_ALGO_AUTO);
     if (rc != LCCRF_OK) return rc;
-    if (!uniforms || !tags) return LCCRF_ENULL;
-    if (!aligned_to(uniforms, 4) || !aligned_to(tags, 4) || (lengths && !aligned_to(lengths, 4))) return LCCRF_EALIGN;
+    if ((!seeded && !uniforms) || !tags) return LCCRF_ENULL;
+    if ((uniforms && !aligned_to(uniforms, 4)) || !aligned_to(tags, 4) || (lengths && !aligned_to(lengths, 4))) return LCCRF_EALIGN;
     const SumWorkspace w = sum_workspace(B, N, T);
     char* base = static_cast<char*>(workspace);
     hipStream_t st = static_cast<hipStream_t>(stream);
@@ -558,10 +559,21 @@ int lccrf_sample(const void* phi, lccrf_dtype dt, const int32_t* lengths, const 
         e = lccrf::launch_full_forward(dt, phi, lengths, B, N, T, ua, ub, Oa, Ob, st);
     }
     if (e == hipSuccess)
-        e = lccrf::launch_backward_sample(dt, phi, lengths, ua, Oa, uniforms, B, N, T,
+        e = lccrf::launch_backward_sample(dt, phi, lengths, ua, Oa, seeded ? nullptr : uniforms, seed, B, N, T,
                                           reinterpret_cast<uint8_t*>(base + w.maps),
                                           reinterpret_cast<uint8_t*>(base + w.winmaps), tags, st);
     return e == hipSuccess ? LCCRF_OK : LCCRF_ELAUNCH;
+}
+
+int lccrf_sample(const void* phi, lccrf_dtype dt, const int32_t* lengths, const float* uniforms, int B, int N, int T,
+                 int32_t* tags, void* workspace, size_t workspace_bytes, void* stream) {
+    return sample_query(phi, dt, lengths, uniforms, false, 0ull, B, N, T, tags, workspace, workspace_bytes, stream);
+}
+
+int lccrf_sample_seeded(const void* phi, lccrf_dtype dt, const int32_t* lengths, uint64_t seed, int B, int N, int T,
+                        int32_t* tags, void* workspace, size_t workspace_bytes, void* stream) {
+    return sample_query(phi, dt, lengths, nullptr, true, (unsigned long long)seed, B, N, T, tags, workspace,
+                        workspace_bytes, stream);
 }
 
 // Common checks of the structured calls.

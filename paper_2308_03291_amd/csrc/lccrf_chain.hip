@@ -516,7 +516,7 @@ __device__ __forceinline__ void forward_half_turned(ChainSmem<G>& sm, float* __r
 
 // ---------------------------------------------------------------------------------------
 // Pass 1: both half chains, vectors stored, nothing else written.
-// STRUCT: potentials are trans + emit (float, T <= 64; a compile-time choice, see lccrf_wave.hip).
+// STRUCT: potentials are trans + emit (float, T <= 128; a compile-time choice, see lccrf_wave.hip).
 template <typename G, typename TIN, bool ALIGNED, int PF, bool STRUCT = false>
 __global__ __launch_bounds__(G::W) void chain_half_kernel(ChainArgs a) {
     __shared__ ChainSmem<G> sm;
@@ -542,7 +542,7 @@ __global__ __launch_bounds__(G::W) void chain_half_kernel(ChainArgs a) {
 
     smem_init<G>(sm, tid);
     __syncthreads();
-    if constexpr (half_turns<G, ALIGNED, PF>()) {
+    if constexpr (half_turns<G, ALIGNED, PF>() && !STRUCT) {  // (structured tiles are formed in registers: nothing to turn)
         if (dir == 0) {
             extern __shared__ __attribute__((aligned(16))) float turn_tiles[];
             forward_half_turned<G, TIN, PF>(sm, turn_tiles, a, sp, tid);
@@ -556,7 +556,7 @@ __global__ __launch_bounds__(G::W) void chain_half_kernel(ChainArgs a) {
     for (int k = 0; k < ITEMS; ++k) dummyI[k] = 0.f;
     double O = 0.0;
     int buf = 0, nstep = 0;
-    // structured potentials (trans tile in registers, emissions streamed): geometries up to T = 64 only
+    // structured potentials (trans tile in registers, emissions streamed): geometries up to T = 128 only
     constexpr bool CAN_STRUCT = STRUCT;
     constexpr bool structured = STRUCT;
     const float* emb = structured ? a.emit + (size_t)b * N * T : nullptr;
@@ -865,10 +865,9 @@ static hipError_t launch_geo(int op, ChainArgs a, hipStream_t st, hipEvent_t bet
     return hipGetLastError();
 }
 
-// Structured potentials at 32 < T <= 64.
-template <bool ALIGNED>
-static hipError_t launch_structured_64(int op, const ChainArgs& a, hipStream_t st, hipEvent_t between) {
-    using G = Geo<16, 4, 4>;
+// Structured potentials at 32 < T <= 128 (G: the geometry of the dense kernels for that tag count).
+template <typename G, bool ALIGNED, int PF2>
+static hipError_t launch_structured_geo(int op, const ChainArgs& a, hipStream_t st, hipEvent_t between) {
     hipLaunchKernelGGL((chain_half_kernel<G, float, ALIGNED, 4, true>), dim3(2 * a.B), dim3(G::W), 0, st, a);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
@@ -880,8 +879,13 @@ static hipError_t launch_structured_64(int op, const ChainArgs& a, hipStream_t s
         hipLaunchKernelGGL(logz_combine_kernel, dim3(a.B), dim3(64), 0, st, a);
         return hipGetLastError();
     }
-    hipLaunchKernelGGL((chain_marginal_kernel<G, float, ALIGNED, 3, true>), dim3(2 * a.B), dim3(G::W), 0, st, a);
+    hipLaunchKernelGGL((chain_marginal_kernel<G, float, ALIGNED, PF2, true>), dim3(2 * a.B), dim3(G::W), 0, st, a);
     return hipGetLastError();
+}
+template <bool ALIGNED>
+static hipError_t launch_structured_sum(int op, const ChainArgs& a, hipStream_t st, hipEvent_t between) {
+    if (a.T <= 64) return launch_structured_geo<Geo<16, 4, 4>, ALIGNED, 3>(op, a, st, between);
+    return launch_structured_geo<Geo<32, 16, 4>, ALIGNED, 2>(op, a, st, between);
 }
 
 template <typename TIN, bool ALIGNED>
@@ -908,7 +912,7 @@ static hipError_t launch_wave(int op, int dtype, const ChainArgs& a, hipStream_t
     return launch_wave_pass(true, dtype, a, st);
 }
 
-bool structured_supported(int T) { return T >= 1 && T <= 64; }
+bool structured_supported(int T) { return T >= 1 && T <= 128; }
 
 // Forward chains over whole sequences, every alpha stored (ua, Oa): the first pass of sampling.
 hipError_t launch_full_forward(int dtype, const void* phi, const int32_t* lengths, int B, int N, int T, float* ua,
@@ -943,7 +947,7 @@ hipError_t launch_sequential_sum(int op, int dtype, const void* phi, const int32
     a.logZ64 = logZ64;
     a.emit = emit;
     a.trans = trans;
-    if (emit && T > 64) return hipErrorInvalidValue;  // the caller checks structured_supported(T) first
+    if (emit && T > 128) return hipErrorInvalidValue;  // the caller checks structured_supported(T) first
     if (wave_supported(T) && op == 1 && !emit && wave_chunks_fused(N - 1)) {
         // Short sequences: both passes in one launch, the vectors in LDS (as for the chunks of the scan).
         if (between) {
@@ -960,7 +964,7 @@ hipError_t launch_sequential_sum(int op, int dtype, const void* phi, const int32
         return launch_wave_logz(dtype, a, st);
     }
     if (wave_supported(T)) return launch_wave(op, dtype, a, st, between);
-    if (emit) return (T % 4) == 0 ? launch_structured_64<true>(op, a, st, between) : launch_structured_64<false>(op, a, st, between);
+    if (emit) return (T % 4) == 0 ? launch_structured_sum<true>(op, a, st, between) : launch_structured_sum<false>(op, a, st, between);
     // Pairs pay off when one workgroup per chain would leave at least half of the chip idle.
     const bool use_pairs = op == 1 && !exact_only && mail && failed && pair_supported(T) && 4 * B <= cus;
     const PairPlan pair{use_pairs ? mail : nullptr, failed, dtype, pair_poll_limit};

@@ -514,12 +514,39 @@ hipError_t launch_cross(bool kl, int dtype, const void* phi_p, const void* phi_q
 // crosses u (weights relative to that total; it equals the sum up to the rounding of the forward
 // step, which matters only for a draw closer than that to the edge of a tag's interval).
 
+// Where the uniforms come from: the caller's array, or (given == null) the counter-based generator
+// Philox4x32-10 (Salmon, Moraes, Dror and Shaw, "Parallel random numbers: as easy as 1, 2, 3", 2011) keyed
+// by the caller's 64-bit seed: the uniform of position i of sequence b is the first output word of the
+// counter (b N + i, 0) under that key, its upper 24 bits times 2^-24.  A draw is a function of (seed, b, i)
+// alone, so a call is reproducible whatever the launch shape, and any draw can be regenerated on its own.
+struct Uniforms {
+    const float* given;
+    unsigned long long seed;
+    __device__ __forceinline__ float at(size_t idx) const {
+        if (given) return given[idx];
+        unsigned c0 = (unsigned)(idx & 0xffffffffull), c1 = (unsigned)(idx >> 32), c2 = 0u, c3 = 0u;
+        unsigned k0 = (unsigned)(seed & 0xffffffffull), k1 = (unsigned)(seed >> 32);
+#pragma unroll
+        for (int round = 0; round < 10; ++round) {
+            const unsigned hi0 = __umulhi(0xD2511F53u, c0), lo0 = 0xD2511F53u * c0;
+            const unsigned hi1 = __umulhi(0xCD9E8D57u, c2), lo1 = 0xCD9E8D57u * c2;
+            c0 = hi1 ^ c1 ^ k0;
+            c1 = lo1;
+            c2 = hi0 ^ c3 ^ k1;
+            c3 = lo0;
+            k0 += 0x9E3779B9u;
+            k1 += 0xBB67AE85u;
+        }
+        return (float)(c0 >> 8) * 0x1p-24f;
+    }
+};
+
 // LPP lanes serve one position (16, 32 or 64: the tag count rounded up), CPT columns a lane (more
 // than one only above 64 tags); a wave serves 64 / LPP positions, a workgroup four waves.
 template <typename TIN, int LPP, int CPT>
 __global__ __launch_bounds__(256) void sample_map_kernel(const TIN* __restrict__ phi, const int32_t* __restrict__ lengths,
                                                          const float* __restrict__ ua, const double* __restrict__ Oa,
-                                                         const float* __restrict__ uniforms, int B, int N, int T,
+                                                         const Uniforms uniforms, int B, int N, int T,
                                                          uint8_t* __restrict__ F) {
     constexpr int PPW = 64 / LPP, TCAP = LPP * CPT;
     __shared__ float alds[4][PPW][TCAP];
@@ -533,7 +560,7 @@ __global__ __launch_bounds__(256) void sample_map_kernel(const TIN* __restrict__
     const size_t TT = (size_t)T * T, vb = (size_t)b * N;
     const TIN* mat = phi + (vb + i + 1) * TT;  // phi_{i+1}
     const float dO = (float)(Oa[vb + i] - Oa[vb + i + 1]);
-    const float u = uniforms[vb + i];
+    const float u = uniforms.at(vb + i);
     float base[CPT], cum[CPT];
     int first[CPT], last[CPT], col[CPT];
 #pragma unroll
@@ -684,7 +711,7 @@ __device__ __forceinline__ int walk_window(const uint8_t* win, uint8_t* segmap, 
 // windows of the table, one after the other.
 template <int K>
 __global__ __launch_bounds__(64) void sample_walk_kernel(const int32_t* __restrict__ lengths, const float* __restrict__ ua,
-                                                         const float* __restrict__ uniforms, const uint8_t* __restrict__ F,
+                                                         const Uniforms uniforms, const uint8_t* __restrict__ F,
                                                          int N, int T, int32_t* __restrict__ tags) {
     __shared__ __attribute__((aligned(16))) uint8_t win[kWalkWindow];
     __shared__ uint8_t segmap[64 * 256];
@@ -695,7 +722,7 @@ __global__ __launch_bounds__(64) void sample_walk_kernel(const int32_t* __restri
     for (int i = L + lane; i < N; i += 64) y[i] = -1;
     if (L == 0) return;
     const size_t vb = (size_t)b * N;
-    int cur = draw_last_tag<K>(ua + (vb + L - 1) * T, uniforms[vb + L - 1], T, lane);
+    int cur = draw_last_tag<K>(ua + (vb + L - 1) * T, uniforms.at(vb + L - 1), T, lane);
     if (cur < 0) {  // no finite path: all tags 0
         for (int i = lane; i < L; i += 64) y[i] = 0;
         return;
@@ -751,7 +778,7 @@ __global__ __launch_bounds__(64) void sample_window_map_kernel(const int32_t* __
 // maps of the windows above (at most W look-ups in LDS) and walks its own positions.
 template <int K>
 __global__ __launch_bounds__(64) void sample_window_walk_kernel(const int32_t* __restrict__ lengths, const float* __restrict__ ua,
-                                                                const float* __restrict__ uniforms, const uint8_t* __restrict__ F,
+                                                                const Uniforms uniforms, const uint8_t* __restrict__ F,
                                                                 int N, int T, int W, const uint8_t* __restrict__ winmap,
                                                                 int32_t* __restrict__ tags) {
     __shared__ __attribute__((aligned(16))) uint8_t win[kWalkWindow];
@@ -767,7 +794,7 @@ __global__ __launch_bounds__(64) void sample_window_walk_kernel(const int32_t* _
     const int wp = kWalkWindow / T;
     const int hi = L - 1 - w * wp;
     const int lo = hi - wp > 0 ? hi - wp : 0;
-    int cur = draw_last_tag<K>(ua + (vb + L - 1) * T, uniforms[vb + L - 1], T, lane);
+    int cur = draw_last_tag<K>(ua + (vb + L - 1) * T, uniforms.at(vb + L - 1), T, lane);
     if (cur < 0) {  // no finite path: all tags 0
         if (w == 0 && lane == 0) y[L - 1] = 0;
         for (int i = lo + lane; i < hi; i += 64) y[i] = 0;
@@ -786,7 +813,7 @@ __global__ __launch_bounds__(64) void sample_window_walk_kernel(const int32_t* _
 
 template <typename TIN>
 static hipError_t launch_sample_T(const TIN* phi, const int32_t* lengths, const float* ua, const double* Oa,
-                                  const float* uniforms, int B, int N, int T, uint8_t* F, uint8_t* winmap, int32_t* tags,
+                                  const Uniforms uniforms, int B, int N, int T, uint8_t* F, uint8_t* winmap, int32_t* tags,
                                   hipStream_t st) {
     if (N > 1) {
         const long long units = (long long)B * (N - 1);
@@ -831,11 +858,12 @@ size_t sample_winmap_bytes(int B, int N, int T) {
 }
 
 hipError_t launch_backward_sample(int dtype, const void* phi, const int32_t* lengths, const float* ua, const double* Oa,
-                                  const float* uniforms, int B, int N, int T, uint8_t* F, uint8_t* winmap, int32_t* tags,
-                                  hipStream_t st) {
+                                  const float* uniforms, unsigned long long seed, int B, int N, int T, uint8_t* F,
+                                  uint8_t* winmap, int32_t* tags, hipStream_t st) {
+    const Uniforms us{uniforms, seed};
     if (dtype == 0)
-        return launch_sample_T(static_cast<const float*>(phi), lengths, ua, Oa, uniforms, B, N, T, F, winmap, tags, st);
-    return launch_sample_T(static_cast<const uint16_t*>(phi), lengths, ua, Oa, uniforms, B, N, T, F, winmap, tags, st);
+        return launch_sample_T(static_cast<const float*>(phi), lengths, ua, Oa, us, B, N, T, F, winmap, tags, st);
+    return launch_sample_T(static_cast<const uint16_t*>(phi), lengths, ua, Oa, us, B, N, T, F, winmap, tags, st);
 }
 
 }  // namespace lccrf

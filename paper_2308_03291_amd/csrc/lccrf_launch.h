@@ -27,9 +27,10 @@ hipError_t launch_sequential_sum(int op, int dtype, const void* phi, const int32
 hipError_t launch_full_forward(int dtype, const void* phi, const int32_t* lengths, int B, int N, int T, float* ua,
                                float* ub, double* Oa, double* Ob, hipStream_t st);
 size_t sample_winmap_bytes(int B, int N, int T);
+// uniforms null: drawn by the counter-based generator under `seed` instead (lccrf_extras.hip, Uniforms).
 hipError_t launch_backward_sample(int dtype, const void* phi, const int32_t* lengths, const float* ua, const double* Oa,
-                                  const float* uniforms, int B, int N, int T, uint8_t* F, uint8_t* winmap, int32_t* tags,
-                                  hipStream_t st);
+                                  const float* uniforms, unsigned long long seed, int B, int N, int T, uint8_t* F,
+                                  uint8_t* winmap, int32_t* tags, hipStream_t st);
 // The forward pass of sampling under the chunked scan: every chunk's forward chain over its whole span from
 // the boundary vectors Fv / OF, every alpha stored (T <= 32).
 hipError_t launch_chunked_full_forward(int dtype, const void* phi, const int32_t* lengths, int B, int N, int T,

@@ -86,11 +86,11 @@ __device__ __forceinline__ VitSpan vit_span(const VitArgs& a, int v) {
     return s;
 }
 
-// STRUCT: potentials are trans + emit (float, T <= 64; a compile-time choice so that the dense path
+// STRUCT: potentials are trans + emit (float, T <= 128; a compile-time choice so that the dense path
 // keeps its loads free of branches).
 template <typename G, typename TIN, bool ALIGNED, bool STRUCT = false>
 __global__ __launch_bounds__(G::W) void viterbi_half_kernel(VitArgs a) {
-    constexpr bool TURNED = vit_turns<G, ALIGNED>();
+    constexpr bool TURNED = vit_turns<G, ALIGNED>() && !STRUCT;  // structured tiles are formed in registers: nothing to turn
     __shared__ VitSmem<G, TURNED> sm;
     constexpr int ITEMS = G::ITEMS;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -628,13 +628,14 @@ template <bool ALIGNED>
 static hipError_t launch_structured_T(const VitArgs& a, hipStream_t st) {
     if (a.T <= 16) return launch_wave_vit<16, float, ALIGNED, true>(a, st);
     if (a.T <= 32) return launch_wave_vit<32, float, ALIGNED, true>(a, st);
-    return launch_structured_geo<Geo<16, 4, 4>, ALIGNED>(a, st);
+    if (a.T <= 64) return launch_structured_geo<Geo<16, 4, 4>, ALIGNED>(a, st);
+    return launch_structured_geo<Geo<32, 16, 4>, ALIGNED>(a, st);
 }
 
-// The same from structured potentials (float emit [B][N][T] + trans [T][T]; T <= 64).
+// The same from structured potentials (float emit [B][N][T] + trans [T][T]; T <= 128).
 hipError_t launch_structured_max(const float* emit, const float* trans, const int32_t* lengths, int B, int N, int T,
                                  uint8_t* bp, double* mid, float* best_score, int32_t* tags, hipStream_t st) {
-    if (T > 64) return hipErrorInvalidValue;
+    if (T > 128) return hipErrorInvalidValue;
     const VitArgs a{nullptr, lengths, B, N, T, bp, mid, best_score, tags, 0, 1, nullptr, emit, trans};
     return (T % 4) == 0 ? launch_structured_T<true>(a, st) : launch_structured_T<false>(a, st);
 }

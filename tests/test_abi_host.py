@@ -116,6 +116,19 @@ def test_tuning_knobs_check_their_range(lib):
         assert lib.lccrf_set_scan_chunk(0) == 0
 
 
+def test_host_philox_known_answers():
+    """The host copy of Philox4x32-10 (tests/philox_host.py), which the seeded sampling test regenerates the
+    library's uniforms with, against the known-answer vectors published with the generator."""
+    import numpy as np
+    import philox_host
+    def one(counter, key):
+        return [int(x) for x in philox_host.philox4x32_10([np.uint64(c) for c in counter], key)]
+    assert one([0, 0, 0, 0], [0, 0]) == [0x6627e8d5, 0xe169c58d, 0xbc57ac4c, 0x9b00dbd8]
+    assert one([0xffffffff] * 4, [0xffffffff] * 2) == [0x408f276d, 0x41c83b0e, 0xa20bc7c6, 0x6d5451fd]
+    u = philox_host.uniforms(12345, 3, 7)
+    assert u.shape == (3, 7) and u.dtype == np.float32 and (u >= 0).all() and (u < 1).all()
+
+
 def test_binding_refuses_cpu_tensors():
     import torch
     with pytest.raises(ValueError):

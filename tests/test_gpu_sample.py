@@ -13,6 +13,7 @@ import torch
 
 from paper_2308_03291_amd import workloads
 from test_gpu_parity import crf  # noqa: F401  (fixture)
+import philox_host
 
 pytestmark = pytest.mark.gpu
 
@@ -169,3 +170,26 @@ def test_sample_frequencies(crf):
 def test_sample_named_workloads(crf, oracle_mod, key):
     w = workloads.WORKLOADS[key]
     _check(crf, oracle_mod, workloads.phi_batch(w), workloads.lengths(w), 11, key, min_exact=0.3)
+
+
+@pytest.mark.parametrize("T,N,seed", [(5, 8, 1), (16, 300, 2 ** 40 + 7), (48, 33, 12345), (128, 40, 2 ** 63 + 5), (32, 700, 99)])
+def test_sample_seeded_matches_the_host_generator(crf, oracle_mod, T, N, seed):
+    """The seeded variant draws its uniforms in the library; regenerated on the host they must give, fed to
+    lccrf_sample, the same tags bit for bit, and fed to the oracle the same tags wherever its margin is clear."""
+    phi, lens = workloads.random_case(8600 + T, 5, N, T, scale=1.5, ragged=True, min_len=1)
+    lens[0] = N
+    dphi, dl = phi.cuda(), lens.cuda()
+    got = crf.lccrf_sample_seeded(dphi, seed, dl)
+    again = crf.lccrf_sample_seeded(dphi, seed, dl)
+    other = crf.lccrf_sample_seeded(dphi, seed + 1, dl)
+    u = philox_host.uniforms(seed, 5, N)
+    fed = crf.lccrf_sample(dphi, torch.from_numpy(u).cuda(), dl)
+    assert torch.equal(got, again) and torch.equal(got, fed)
+    assert not torch.equal(got, other)
+    want, margin = oracle_mod.sample(phi, u, lens.numpy())
+    g = got.cpu().numpy()
+    for b in range(5):
+        if margin[b] > MARGIN:
+            assert np.array_equal(g[b], want[b]), f"sequence {b} (margin {margin[b]:.2e})"
+    lp = oracle_mod.log_prob(phi, g, lens.numpy())
+    assert np.isfinite(lp).all()

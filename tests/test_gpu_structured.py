@@ -55,7 +55,7 @@ def _check(crf, oracle_mod, emit, trans, lens, what):
 
 
 @pytest.mark.parametrize("T,N", [(1, 4), (2, 9), (5, 8), (9, 33), (16, 40), (17, 12), (32, 65), (33, 7), (45, 50), (48, 33),
-                                 (64, 20), (63, 5)])
+                                 (64, 20), (63, 5), (65, 9), (100, 21), (127, 6), (128, 40)])
 def test_structured_sweep(crf, oracle_mod, T, N):
     emit, trans = _make(7000 + 17 * T + N, 5, N, T)
     lens = torch.tensor([N, max(N - 1, 0), min(2, N), 1, 0], dtype=torch.int32)
@@ -94,6 +94,6 @@ def test_structured_agrees_with_dense_call(crf):
 
 
 def test_structured_needs_a_supported_tag_set(crf):
-    emit, trans = _make(7300, 2, 6, 65)
+    emit, trans = _make(7300, 2, 6, 129)
     with pytest.raises(crf.LccrfError, match="not available"):
         crf.lccrf_log_partition_structured(emit.cuda(), trans.cuda())
