@@ -35,66 +35,11 @@
 // correction (kappa) to the next, so rounding drift between the forward and the backward
 // offsets (a random walk over thousands of float32 steps) never builds up in the output.
 #include "lccrf_chain_args.h"
+#include "lccrf_chain_smem.h"
 #include "lccrf_device.h"
 #include "lccrf_launch.h"
 
 namespace lccrf {
-
-template <typename G>
-struct ChainSmem {
-    alignas(16) float pmax[G::WAVES][G::TCAP];  // per-wave column maxima of x = ua(s) + phi2(s,t) ...
-    alignas(16) float psum[G::WAVES][G::TCAP];  // ... and column sums of 2^(x - that maximum)
-    alignas(16) float rvec[2][G::TCAP];         // un-normalised result vector of a step (double buffered)
-    alignas(16) float wmax[2][16];              // per-wave maxima of rvec (normaliser = their maximum)
-    alignas(16) float wtot[2][16];              // per-wave sums of the marginals written by a step
-    alignas(16) float red[2][4];                // scratch for the mid-point log-sum-exp
-    int bad[4];                                 // "speculative step n rejected", indexed by n & 3
-};
-
-template <typename G>
-__device__ __forceinline__ void smem_init(ChainSmem<G>& sm, int tid) {
-    for (int k = tid; k < 2 * G::TCAP; k += G::W) (&sm.rvec[0][0])[k] = LCCRF_NEG_INF;
-    if (tid < 32) (&sm.wmax[0][0])[tid] = LCCRF_NEG_INF;
-    if (tid < 32) (&sm.wtot[0][0])[tid] = 0.f;
-    if (tid < 4) sm.bad[tid] = 0;
-}
-
-
-// Normaliser of the vector in rvec[buf]: its maximum (0 if the vector is all -inf).
-template <typename G>
-__device__ __forceinline__ float read_shift(const ChainSmem<G>& sm, int buf) {
-    float d = LCCRF_NEG_INF;
-#pragma unroll
-    for (int w = 0; w < 16; w += 4) {
-        const float4 q = *reinterpret_cast<const float4*>(&sm.wmax[buf][w]);
-        d = fmaxf(fmaxf(d, fmaxf(q.x, q.y)), fmaxf(q.z, q.w));
-    }
-    return finite_or_zero(d);
-}
-
-// -log2 of the sum of the marginals the last step wrote (0 if nothing usable was written).
-template <typename G>
-__device__ __forceinline__ float read_drift(const ChainSmem<G>& sm, int buf) {
-    float tot = 0.f;
-#pragma unroll
-    for (int w = 0; w < 16; w += 4) {
-        const float4 q = *reinterpret_cast<const float4*>(&sm.wtot[buf][w]);
-        tot += (q.x + q.y) + (q.z + q.w);
-    }
-    return (tot > 0.5f && tot < 2.0f) ? -lg2(tot) : 0.f;
-}
-
-// Publish r (one value per column thread, -inf for t >= T) as the next vector.
-// r must be -inf in every lane that owns no column; the wave-wide exchange runs with all
-// lanes of the (wave-uniformly selected) column waves active.
-template <typename G>
-__device__ __forceinline__ void publish_columns(ChainSmem<G>& sm, int nbuf, int tid, float r) {
-    if ((tid >> 6) < G::COLWAVES) {
-        if (tid < G::TCAP) sm.rvec[nbuf][tid] = r;
-        const float wm = xor_max<1, 64>(r);
-        if ((tid & 63) == 0) sm.wmax[nbuf][tid >> 6] = wm;
-    }
-}
 
 // Tiles arrive with clamped addresses: entries outside the T x T matrix hold finite copies of
 // in-range data.  They never reach a result: rows s >= T carry ua = -inf (forward) or are
@@ -626,32 +571,6 @@ __global__ __launch_bounds__(G::W) void chain_half_kernel(ChainArgs a) {
     }
 }
 
-// log2 Z from the two vectors stored for the meeting position h.  Every thread of the
-// workgroup returns the same value.
-template <typename G>
-__device__ __forceinline__ double midpoint_log2z(ChainSmem<G>& sm, const ChainArgs& a, size_t vb, int h, int T, int tid) {
-    float z = LCCRF_NEG_INF;
-    if (tid < T) z = a.ua[(vb + h) * T + tid] + a.ub[(vb + h) * T + tid];
-    if ((tid >> 6) < G::COLWAVES) {
-        const float wm = xor_max<1, 64>(z);
-        if ((tid & 63) == 0) sm.red[0][tid >> 6] = wm;
-    }
-    __syncthreads();
-    float M = LCCRF_NEG_INF;
-#pragma unroll
-    for (int w = 0; w < G::COLWAVES; ++w) M = fmaxf(M, sm.red[0][w]);
-    const float g = finite_or_zero(M);
-    if ((tid >> 6) < G::COLWAVES) {
-        const float ws = xor_sum<1, 64>(ex2(z - g));  // z = -inf outside the T columns: adds 0
-        if ((tid & 63) == 0) sm.red[1][tid >> 6] = ws;
-    }
-    __syncthreads();
-    float S = 0.f;
-#pragma unroll
-    for (int w = 0; w < G::COLWAVES; ++w) S += sm.red[1][w];
-    return (double)(M + lg2(S)) + a.Oa[vb + h] + a.Ob[vb + h];
-}
-
 // ---------------------------------------------------------------------------------------
 // Pass 2: both chains continue past the meeting point and write the marginals.
 template <typename G, typename TIN, bool ALIGNED, int PF, bool STRUCT = false>
@@ -893,7 +812,7 @@ static hipError_t launch_T(int op, const ChainArgs& a, hipStream_t st, hipEvent_
     const int T = a.T;  // T <= 32 is served by the one-wave kernels (launch_wave)
     if (T <= 64) return launch_geo<Geo<16, 4, 4>, TIN, ALIGNED, 4, 3>(op, a, st, between, pair);
     if (T <= 128) return launch_geo<Geo<32, 16, 4>, TIN, ALIGNED, 4, 2>(op, a, st, between, pair);
-    return launch_geo<Geo<64, 16, 16>, TIN, ALIGNED, 1, 1>(op, a, st, between, pair);
+    return hipErrorInvalidValue;  // larger tag sets take the row-batch kernels (launch_stream)
 }
 
 // Both passes with one wave per chain (T <= 32).
@@ -912,6 +831,22 @@ static hipError_t launch_wave(int op, int dtype, const ChainArgs& a, hipStream_t
     return launch_wave_pass(true, dtype, a, st);
 }
 
+// Both passes in row batches (128 < T <= 256).
+static hipError_t launch_stream(int op, int dtype, const ChainArgs& a, hipStream_t st, hipEvent_t between) {
+    hipError_t e = launch_stream_pass(false, dtype, a, st);
+    if (e != hipSuccess) return e;
+    if (between) {
+        e = hipEventRecord(between, st);
+        if (e != hipSuccess) return e;
+    }
+    if (op == 2) return hipSuccess;  // first pass only
+    if (op == 0) {
+        hipLaunchKernelGGL(logz_combine_kernel, dim3(a.B), dim3(64), 0, st, a);
+        return hipGetLastError();
+    }
+    return launch_stream_pass(true, dtype, a, st);
+}
+
 bool structured_supported(int T) { return T >= 1 && T <= 128; }
 
 // Forward chains over whole sequences, every alpha stored (ua, Oa): the first pass of sampling.
@@ -920,6 +855,7 @@ hipError_t launch_full_forward(int dtype, const void* phi, const int32_t* length
     ChainArgs a{phi, lengths, B, N, T, ua, ub, Oa, Ob, nullptr, nullptr, 0, nullptr, 0, 1, nullptr, nullptr, nullptr, nullptr};
     a.full_forward = 1;
     if (wave_supported(T)) return launch_wave(2, dtype, a, st, nullptr);
+    if (stream_supported(T)) return launch_stream(2, dtype, a, st, nullptr);
     const PairPlan pair{nullptr, nullptr, dtype, 0};
     const bool aligned = (T % 4) == 0;
     if (dtype == 0)
@@ -965,6 +901,7 @@ hipError_t launch_sequential_sum(int op, int dtype, const void* phi, const int32
     }
     if (wave_supported(T)) return launch_wave(op, dtype, a, st, between);
     if (emit) return (T % 4) == 0 ? launch_structured_sum<true>(op, a, st, between) : launch_structured_sum<false>(op, a, st, between);
+    if (stream_supported(T)) return launch_stream(op, dtype, a, st, between);
     // Pairs pay off when one workgroup per chain would leave at least half of the chip idle.
     const bool use_pairs = op == 1 && !exact_only && mail && failed && pair_supported(T) && 4 * B <= cus;
     const PairPlan pair{use_pairs ? mail : nullptr, failed, dtype, pair_poll_limit};

@@ -101,6 +101,10 @@ hipError_t launch_wave_pass(bool second_pass, int dtype, const ChainArgs& a, hip
 // launch, one workgroup of two waves per chunk, the chunk's vectors in LDS (ua, ub, Oa, Ob unused).
 hipError_t launch_wave_logz(int dtype, const ChainArgs& a, hipStream_t st);  // whole sequences, logZ only, one launch
 bool wave_chunks_fused(int chunk);
+// Row-batch kernels for 128 < T <= 256 (lccrf_stream.hip): one pass over whole sequences, vectors and
+// marginals exactly as launch_wave_pass.
+bool stream_supported(int T);
+hipError_t launch_stream_pass(bool second_pass, int dtype, const ChainArgs& a, hipStream_t st);
 hipError_t launch_wave_chunks(int dtype, const ChainArgs& a, hipStream_t st);
 
 }  // namespace lccrf

@@ -333,6 +333,145 @@ __global__ __launch_bounds__(G::W) void viterbi_half_kernel(VitArgs a) {
     if (tid < T) mid[tid] = sm.dvec[buf][tid];
 }
 
+// 129 .. 256 tags: the matrix of a position streams through registers in batches of 64 rows, as in the
+// sum-product kernels for these tag sets (lccrf_stream.hip): lane l of wave w holds, of batch q, rows
+// 64 q + 4 w + k (k < 4), columns 4 l .. 4 l + 3, and a ring of batch slots is refilled across position
+// boundaries.  Held as one tile of 64 potentials a thread beside the double-precision candidates, the
+// matrix spilled registers and allowed no load in flight during a step.
+//   forward:  a thread keeps the best candidate of each of its four columns over its rows of all batches
+//             (ascending rows: the first maximum wins), the 16 waves' candidates meet through LDS;
+//   backward: a row is complete inside its wave and batch: four rows at a time by the packed reduction.
+constexpr int kVitBatchRows = 64;
+constexpr int kVitRing = 3;
+using VSG = Geo<64, 16, 16>;
+
+template <typename TIN, bool ALIGNED>
+__global__ __launch_bounds__(1024) void viterbi_stream_kernel(VitArgs a) {
+    __shared__ VitSmem<VSG, false> sm;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int dir = blockIdx.x & 1;
+    const VitSpan sp = vit_span(a, blockIdx.x >> 1);
+    if (sp.empty) return;
+    const int b = sp.b, N = a.N, T = a.T;
+    const int p0 = sp.p0, e = sp.e, h = meeting_point(p0, e);
+    const int c4 = 4 * lane;
+    const size_t TT = (size_t)T * T;
+    const TIN* phib = static_cast<const TIN*>(a.phi) + (size_t)b * N * TT;
+    uint8_t* bpb = a.bp + (size_t)b * N * T;
+    double* mid = a.mid + (((size_t)b * a.C + sp.c) * 2 + dir) * T;
+    const double ninf = -__builtin_huge_val();
+    const int NBq = (T + kVitBatchRows - 1) / kVitBatchRows;  // 3 or 4
+
+    for (int k = tid; k < 2 * VSG::TCAP; k += 1024) (&sm.dvec[0][0])[k] = ninf;
+    __syncthreads();
+    if (tid < T) {
+        if (dir == 0) {
+            if (sp.t0 == 0) sm.dvec[0][tid] = (double)Elem<TIN>::get(phib + tid);
+            else sm.dvec[0][tid] = (tid == a.pin[(size_t)b * a.C + sp.c - 1]) ? 0.0 : ninf;
+        } else {
+            sm.dvec[0][tid] = (a.chunk <= 0 || tid == a.pin[(size_t)b * a.C + sp.c]) ? 0.0 : ninf;
+        }
+    }
+    __syncthreads();
+
+    int buf = 0;
+    float ring[kVitRing][4][4];
+    const int first = dir == 0 ? p0 + 1 : e;
+    const int n = dir == 0 ? h - p0 : e - h;
+    const int sdir = dir == 0 ? +1 : -1;
+    // unit u = batch u % NBq of the matrix of position first + sdir (u / NBq); addresses clamped into the matrix
+    auto load = [&](int u, int slot) {
+        const TIN* mat = phib + (size_t)(first + sdir * (u / NBq)) * TT;
+        const int row0 = kVitBatchRows * (u % NBq) + 4 * wave;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const int s = row0 + k;
+            const TIN* row = mat + (size_t)(s < T ? s : T - 1) * T;
+            if (ALIGNED) {
+                Elem<TIN>::get4_stream(row + (c4 < T ? c4 : T - 4), ring[slot][k]);
+            } else {
+#pragma unroll
+                for (int j = 0; j < 4; ++j) ring[slot][k][j] = Elem<TIN>::get(row + (c4 + j < T ? c4 + j : T - 1));
+            }
+        }
+    };
+    if (dir == 0) {
+        double best[4] = {ninf, ninf, ninf, ninf};
+        int arg[4] = {kNoArg, kNoArg, kNoArg, kNoArg};
+        walk<kVitRing>(0, n * NBq - 1, +1, load, [&](int u, int slot) {
+            const int i = first + u / NBq, q = u % NBq;
+            const int row0 = kVitBatchRows * q + 4 * wave;
+            if (q == 0) {
+#pragma unroll
+                for (int j = 0; j < 4; ++j) { best[j] = ninf; arg[j] = kNoArg; }
+            }
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {  // ascending rows: the first maximum wins
+                const int s = row0 + k;
+                const double dk = sm.dvec[buf][s];  // -inf for rows >= T (s < 256 always)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const double val = dk + (double)ring[slot][k][j];
+                    if (val > best[j]) { best[j] = val; arg[j] = s; }
+                }
+            }
+            if (q == NBq - 1) {
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    sm.pv[wave][c4 + j] = best[j];
+                    sm.pi[wave][c4 + j] = arg[j];
+                }
+                __syncthreads();
+                if (tid < VSG::TCAP) {
+                    double bv = ninf;
+                    int ba = kNoArg;
+                    if (tid < T) {
+#pragma unroll
+                        for (int w = 0; w < 16; ++w) take_better(bv, ba, sm.pv[w][tid], sm.pi[w][tid]);
+                        bpb[(size_t)i * T + tid] = (uint8_t)(ba == kNoArg ? 0 : ba);
+                    }
+                    sm.dvec[buf ^ 1][tid] = bv;
+                }
+                __syncthreads();
+                buf ^= 1;
+            }
+        });
+    } else {
+        double ek[4] = {ninf, ninf, ninf, ninf};
+        walk<kVitRing>(0, n * NBq - 1, +1, load, [&](int u, int slot) {
+            const int i = first - u / NBq, q = u % NBq;
+            const int row0 = kVitBatchRows * q + 4 * wave;
+            if (q == 0) {
+#pragma unroll
+                for (int j = 0; j < 4; ++j) ek[j] = sm.dvec[buf][c4 + j];  // -inf for tags >= T
+            }
+            Best c[4];
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                c[k] = Best{ninf, kNoArg};
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {  // ascending columns: the first maximum wins
+                    const double val = (double)ring[slot][k][j] + ek[j];
+                    if (val > c[k].v) c[k] = Best{val, c4 + j};
+                }
+            }
+            // four rows at a time: each lane ends up with the winner of one of them
+            const int kk = 2 * (lane & 1) + ((lane >> 1) & 1);
+            const Best w = reduce4_best_over_lanes<64>(c[0], c[1], c[2], c[3], lane);
+            const int s = row0 + kk;
+            if (lane < 4 && s < T) {
+                sm.dvec[buf ^ 1][s] = w.v;
+                bpb[(size_t)i * T + s] = (uint8_t)(w.a == kNoArg ? 0 : w.a);
+            }
+            if (q == NBq - 1) {
+                __syncthreads();
+                buf ^= 1;
+            }
+        });
+    }
+    if (tid < T) mid[tid] = sm.dvec[buf][tid];
+}
+
 // The first maximum of val[0 .. n-1] (arg ascending with the index) ends in val[0] / arg[0]: a tree
 // of pairwise comparisons in which the right-hand candidate wins only if strictly greater, so the
 // chain of dependent instructions is log2 n long instead of n.
@@ -600,7 +739,11 @@ static hipError_t launch_T(const VitArgs& a, hipStream_t st) {
     if (T <= 32) return launch_wave_vit<32, TIN, ALIGNED, false>(a, st);
     if (T <= 64) return launch_geo<Geo<16, 4, 4>, TIN, ALIGNED>(a, st);
     if (T <= 128) return launch_geo<Geo<32, 16, 4>, TIN, ALIGNED>(a, st);
-    return launch_geo<Geo<64, 16, 16>, TIN, ALIGNED>(a, st);
+    hipLaunchKernelGGL((viterbi_stream_kernel<TIN, ALIGNED>), dim3(2 * a.B * a.C), dim3(1024), 0, st, a);
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(viterbi_trace_kernel, dim3(a.B * a.C), dim3(128), 0, st, a);
+    return hipGetLastError();
 }
 
 static hipError_t launch_any(int dtype, const VitArgs& a, hipStream_t st) {

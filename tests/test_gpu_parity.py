@@ -144,6 +144,35 @@ def test_largest_tag_sets(crf, oracle_mod, T):
     check_case(crf, oracle_mod, phi, lens, what=f"T={T}")
 
 
+@pytest.mark.parametrize("T,dtype", [(129, "f32"), (192, "f32"), (193, "f32"), (250, "f32"), (256, "f32"), (200, "bf16"), (255, "bf16")])
+def test_largest_tag_sets_long_chains(crf, oracle_mod, T, dtype):
+    """129 .. 256 tags stream every matrix in batches of 64 rows (three batches up to 192 tags, four above):
+    chains of 70 positions, ragged, with the speculative and the exact step, marginals and paths."""
+    N = 70
+    phi, _ = workloads.random_case(3050 + T, 4, N, T, scale=3.0 if dtype == "bf16" else 1.5, dtype=dtype)
+    lens = torch.tensor([N, 1, N // 2, N - 1], dtype=torch.int32)
+    check_case(crf, oracle_mod, phi, lens, poison=dtype == "f32", what=f"T={T} N={N} {dtype}")
+    check_case(crf, oracle_mod, phi, lens, poison=False, algo=crf.ALGO_SEQUENTIAL_EXACT, what=f"exact T={T} N={N} {dtype}",
+               queries=("logz", "mu"))
+
+
+def test_largest_tag_sets_forbidden_edges_and_jumps(crf, oracle_mod):
+    """The exact replay of the row-batch kernels (the matrix streamed again from memory): -inf potentials, a
+    chain without a finite path, and scales that jump by hundreds of nats between positions."""
+    T, N = 160, 24
+    phi, _ = workloads.random_case(3060, 4, N, T)
+    ninf = float("-inf")
+    phi[0, 5, :, 7] = ninf
+    phi[0, 9, 3, :] = ninf
+    phi[1, 8, :, :] = ninf                       # no finite path at all
+    phi[2, 3] += 400.0
+    phi[2, 15] -= 400.0
+    mask = torch.rand(N, T, T, generator=torch.Generator().manual_seed(5)) < 0.7
+    phi[3][mask] = ninf
+    phi[3, :, torch.arange(T), torch.arange(T)] = 0.0
+    check_case(crf, oracle_mod, phi, None, poison=False, what="T=160 -inf and jumps", queries=("logz", "mu"))
+
+
 def test_lengths_none_means_full(crf, oracle_mod):
     phi, _ = workloads.random_case(3100, 3, 9, 12)
     check_case(crf, oracle_mod, phi, None, what="lengths=None")
