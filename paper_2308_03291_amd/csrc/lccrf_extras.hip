@@ -124,8 +124,12 @@ static hipError_t launch_entropy_combine(const ChainArgs& a, float* H, hipStream
 // weight zero contributes nothing whatever psi holds there.  In modes 1 and 2 a common shift of
 // h (its largest finite entry) moves into a double-precision offset at every step, so the vector
 // stays small however long the chain is.
-// Plain exact steps (every sum against its own maximum), a secondary query: the forward step
-// takes the column maxima through LDS first, then the sums.
+// The entropy (mode 0) at 33 .. 128 tags first tries every step with one shift for the whole matrix, the
+// normaliser of the vector it starts from, as the chain kernels do (lccrf_chain.hip): U / S + log2 S does not
+// depend on the shift as long as no term that matters is flushed, which holds if every sum lies in
+// [2^-60, 2^60]; otherwise the step is replayed exactly on the same registers.  The other modes and
+// geometries take plain exact steps (every sum against its own maximum): the forward step takes the
+// column maxima through LDS first, then the sums.
 template <typename G>
 struct EntropySmem {
     alignas(16) float pmax[G::WAVES][G::TCAP];
@@ -134,6 +138,7 @@ struct EntropySmem {
     alignas(16) float rvec[2][G::TCAP];
     alignas(16) float hvec[2][G::TCAP];
     alignas(16) float wmax[2][16];
+    int bad[4];  // "speculative step n rejected", indexed by n & 3
 };
 
 template <typename TIN, bool ALIGNED>
@@ -160,6 +165,7 @@ __global__ __launch_bounds__(G::W) void entropy_half_kernel(ChainArgs a) {
     constexpr bool LATE_PSI = CROSS && G::WAVES >= 16;
     constexpr bool QRING = CROSS && !LATE_PSI;
     constexpr int QITEMS = QRING ? ITEMS : 1, QPF = QRING ? PF : 1;
+    constexpr bool SPEC = !CROSS && ITEMS == 4 && G::LPR >= 16;  // speculative step first
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int b = blockIdx.x >> 1, dir = blockIdx.x & 1;
     const int N = a.N, T = a.T;
@@ -176,6 +182,8 @@ __global__ __launch_bounds__(G::W) void entropy_half_kernel(ChainArgs a) {
         (&sm.hvec[0][0])[k] = 0.f;
     }
     if (tid < 32) (&sm.wmax[0][0])[tid] = LCCRF_NEG_INF;
+    if (tid < 4) sm.bad[tid] = 0;
+    int nstep = 0;
     __syncthreads();
     if (tid < T) {
         const float p0 = Elem<TIN>::get(phib + tid);
@@ -237,6 +245,58 @@ __global__ __launch_bounds__(G::W) void entropy_half_kernel(ChainArgs a) {
                 const int s = r0 + k * G::RPP;
                 ua[k] = (s < T) ? sm.rvec[buf][s] - d : LCCRF_NEG_INF;
                 hin[k] = (s < T) ? sm.hvec[buf][s] - c : 0.f;
+            }
+            if constexpr (SPEC) {
+                // one shift for the whole matrix: the normaliser d predicts this step's growth
+                const int flag = nstep & 3;
+                if (tid == 0) sm.bad[(nstep + 1) & 3] = 0;
+                float ls[4] = {0.f, 0.f, 0.f, 0.f}, lu[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int k = 0; k < ITEMS; ++k) {
+                    const float uac = ua[k] - d;
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        const float arg = __builtin_fmaf(x[k][j], kLog2e, uac);
+                        const float ex = ex2(arg);
+                        ls[j] += ex;
+                        lu[j] = __builtin_fmaf(ex, hin[k] - log2_term(arg), lu[j]);
+                    }
+                }
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    ls[j] = xor_sum<G::LPR, 64>(ls[j]);
+                    lu[j] = xor_sum<G::LPR, 64>(lu[j]);
+                }
+                if (lane < G::LPR) {
+                    *reinterpret_cast<float4*>(&sm.psum[wave][c4]) = make_float4(ls[0], ls[1], ls[2], ls[3]);
+                    *reinterpret_cast<float4*>(&sm.pU[wave][c4]) = make_float4(lu[0], lu[1], lu[2], lu[3]);
+                }
+                __syncthreads();
+                if (wave < G::COLWAVES) {
+                    bool good = true;
+                    if (tid < T) {
+                        float S = 0.f, U = 0.f;
+#pragma unroll
+                        for (int w = 0; w < G::WAVES; ++w) {
+                            S += sm.psum[w][tid];
+                            U += sm.pU[w][tid];
+                        }
+                        good = sum_in_range(S);
+                        sm.rvec[buf ^ 1][tid] = d + lg2(S);
+                        sm.hvec[buf ^ 1][tid] = entropy_of(U, S);
+                    }
+                    if (!__all(good) && lane == 0) sm.bad[flag] = 1;
+                }
+                __syncthreads();
+                ++nstep;
+                if (sm.bad[flag] == 0) {
+                    buf ^= 1;
+                    return;
+                }
+                __syncthreads();  // nobody still reads the flag or the rejected vectors
+            }
+#pragma unroll
+            for (int k = 0; k < ITEMS; ++k) {
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
                     const float xs = __builtin_fmaf(x[k][j], kLog2e, ua[k]);
@@ -308,6 +368,41 @@ __global__ __launch_bounds__(G::W) void entropy_half_kernel(ChainArgs a) {
             for (int j = 0; j < 4; ++j) {
                 ub[j] = (c4 + j < T) ? sm.rvec[buf][c4 + j] - d : LCCRF_NEG_INF;
                 hin[j] = (c4 + j < T) ? sm.hvec[buf][c4 + j] - c : 0.f;
+            }
+            if constexpr (SPEC) {
+                const int flag = nstep & 3;
+                if (tid == 0) sm.bad[(nstep + 1) & 3] = 0;
+                float Sl[ITEMS], Ul[ITEMS];
+#pragma unroll
+                for (int k = 0; k < ITEMS; ++k) {
+                    Sl[k] = 0.f;
+                    Ul[k] = 0.f;
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        const float arg = __builtin_fmaf(y[k][j], kLog2e, ub[j] - d);
+                        const float ex = ex2(arg);
+                        Sl[k] += ex;
+                        Ul[k] = __builtin_fmaf(ex, hin[j] - log2_term(arg), Ul[k]);
+                    }
+                }
+                // four rows at a time: each lane ends up with the complete sums of one of them
+                const int kk = 2 * (lane & 1) + ((lane >> 1) & 1);
+                const float S = reduce4_over_lanes<G::LPR>(Sl[0], Sl[1], Sl[2], Sl[3], lane);
+                const float U = reduce4_over_lanes<G::LPR>(Ul[0], Ul[1], Ul[2], Ul[3], lane);
+                const int s = r0 + kk * G::RPP;
+                if ((tid % G::LPR) < 4 && s < T) {
+                    sm.rvec[buf ^ 1][s] = d + lg2(S);
+                    sm.hvec[buf ^ 1][s] = entropy_of(U, S);
+                }
+                const bool good = s >= T || sum_in_range(S);
+                if (!__all(good) && lane == 0) sm.bad[flag] = 1;
+                __syncthreads();
+                ++nstep;
+                if (sm.bad[flag] == 0) {
+                    buf ^= 1;
+                    return;
+                }
+                __syncthreads();  // nobody still reads the flag or the rejected vectors
             }
 #pragma unroll
             for (int k = 0; k < ITEMS; ++k) {
