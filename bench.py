@@ -241,6 +241,8 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="cfg4")
+    ap.add_argument("--algo", default="auto", choices=("auto", "sequential", "scan"),
+                    help="schedule of the timed marginals call (profiles of a schedule AUTO would not take)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-other-queries", action="store_true")
     ap.add_argument("--no-per-config", action="store_true")
@@ -310,12 +312,14 @@ def main():
         if args.cold:
             scratch.add_(1)
 
+    algo = {"auto": crf.ALGO_AUTO, "sequential": crf.ALGO_SEQUENTIAL, "scan": crf.ALGO_SCAN}[args.algo]
+
     def run_step(evs=None):
         evict()
         if evs is None:
-            crf.lccrf_marginals(phi, lens, out=mu, logZ=lz, workspace=ws)
+            crf.lccrf_marginals(phi, lens, out=mu, logZ=lz, workspace=ws, algo=algo)
         else:
-            crf.lccrf_marginals_timed(phi, lens, mu, lz, ws, evs)
+            crf.lccrf_marginals_timed(phi, lens, mu, lz, ws, evs, algo)
 
     for _ in range(args.warmup):
         run_step()
@@ -340,18 +344,23 @@ def main():
 
     value = pots / (ms_per_step * 1e-3)
     call_bytes = eff_pots * (2 * esz + 4)
-    if crf.auto_algo(crf.OP_MARGINALS, w.B, w.N, w.T) == crf.ALGO_SCAN or (w.T <= 32 and 2 <= w.N <= 65):
+    scan_taken = algo == crf.ALGO_SCAN or (algo == crf.ALGO_AUTO and crf.auto_algo(crf.OP_MARGINALS, w.B, w.N, w.T) == crf.ALGO_SCAN)
+    if w.T <= 32 and (scan_taken or 2 <= w.N <= 65):
         # Chunked scan: the interval after the boundary phases is one kernel that makes both passes over
         # every chunk (two reads of phi, the second from cache at best, and one write of mu).  Sequences of
         # at most 65 positions over at most 32 tags take the same kernel whole.
         kernel, alg_bytes = "wave_chunk_kernel", call_bytes
+    elif scan_taken:
+        # 33 .. 64 tags under the scan: after the boundary phases the chunks run the two passes of the chain kernels
+        kernel, alg_bytes = "chain_marginal_kernel (chunks; the interval also holds the chunks' first pass)", call_bytes
     else:
         # dominant kernel: second pass = one read of phi + one write of mu over the positions in the chains.
         # With few sequences and T = 128 that pass is the two-workgroups-per-chain kernel (plus two
         # few-microsecond helpers the event interval also covers: mailbox reset, exact fix-up launch).
         alg_bytes = eff_pots * (esz + 4)
         paired = w.T == 128 and 4 * w.B <= torch.cuda.get_device_properties(dev).multi_processor_count
-        kernel = "pair_marginal_kernel" if paired else ("wave_marginal_kernel" if w.T <= 32 else "chain_marginal_kernel")
+        kernel = "pair_marginal_kernel" if paired else ("wave_marginal_kernel" if w.T <= 32 else
+                                                        "stream_chain_kernel" if w.T > 128 else "chain_marginal_kernel")
     achieved = alg_bytes / (pass2_avg * 1e-3) / 1e9
     roofline = {"bound": "hbm", "kernel": kernel,
                 "achieved": achieved, "peak": HBM_PEAK_GBPS,
@@ -462,7 +471,8 @@ def main():
         "data": "synthetic",
         "config": {"workload": f"{w.key}: B={w.B} N={w.N} T={w.T} {w.dtype} phi, lengths U[{w.len_lo},{w.len_hi}], "
                                f"seeded {w.kind} potentials (scale {w.scale})",
-                   "query": "lccrf_marginals (logZ + all edge marginals)", "caches": "cold" if args.cold else "warm",
+                   "query": "lccrf_marginals (logZ + all edge marginals)", "schedule": args.algo,
+                   "caches": "cold" if args.cold else "warm",
                    "potentials": pots,
                    "effective_potentials": eff_pots},
         "roofline": roofline, "cpu_baseline": base,

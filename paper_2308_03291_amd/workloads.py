@@ -64,6 +64,9 @@ WORKLOADS = {
                             "the size the paper times its linear-chain CRF on"),
     "paper_hmm": Workload("paper_hmm", 7, 1, 128, 32, "f32", 128, 128, "iid", 1.0,
                           "the size the paper lists for its HMM"),
+    # Beyond the five configurations: the largest tag set the library serves (profiles, timing sweeps).
+    "t256": Workload("t256", 8, 64, 256, 256, "f32", 256, 256, "iid", 1.0,
+                     "largest tag set: 4.3 GB of potentials, matrices streamed in row batches"),
 }
 
 
