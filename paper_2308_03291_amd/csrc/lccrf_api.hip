@@ -599,6 +599,26 @@ static int structured_sum(int op, const float* emit, const float* trans, const i
     if ((logZ && !aligned_to(logZ, 4)) || (marginals && !aligned_to(marginals, 16))) return LCCRF_EALIGN;
     const SumWorkspace w = sum_workspace(B, N, T);
     char* base = static_cast<char*>(workspace);
+    if (scan_pays_sum(B, N, T)) {  // the schedule lccrf_auto_algo reports for the dense call of this shape
+        hipStream_t st = static_cast<hipStream_t>(stream);
+        float* Fv = reinterpret_cast<float*>(base + w.Fv);
+        double* OF = reinterpret_cast<double*>(base + w.OF);
+        float* Gv = reinterpret_cast<float*>(base + w.Gv);
+        double* OG = reinterpret_cast<double*>(base + w.OG);
+        hipError_t e = lccrf::launch_scan_boundaries(LCCRF_F32, nullptr, lengths, B, N, T, scan_chunk(B, N, T),
+                                                     reinterpret_cast<float*>(base + w.Pl),
+                                                     reinterpret_cast<float*>(base + w.rel),
+                                                     reinterpret_cast<double*>(base + w.base), Fv, OF, Gv, OG,
+                                                     group_buffers(w, base), logZ, op == 1, st, nullptr, emit, trans);
+        if (e == hipSuccess && op == 1)
+            e = lccrf::launch_chunked_marginals(LCCRF_F32, nullptr, lengths, B, N, T,
+                                                reinterpret_cast<float*>(base + w.ua),
+                                                reinterpret_cast<float*>(base + w.ub),
+                                                reinterpret_cast<double*>(base + w.Oa),
+                                                reinterpret_cast<double*>(base + w.Ob), marginals, scan_chunk(B, N, T),
+                                                Fv, OF, Gv, OG, st, nullptr, false, nullptr, nullptr, false, emit, trans);
+        return e == hipSuccess ? LCCRF_OK : LCCRF_ELAUNCH;
+    }
     const hipError_t e = lccrf::launch_sequential_sum(
         op, LCCRF_F32, nullptr, lengths, B, N, T, reinterpret_cast<float*>(base + w.ua),
         reinterpret_cast<float*>(base + w.ub), reinterpret_cast<double*>(base + w.Oa),
@@ -627,6 +647,21 @@ int lccrf_argmax_structured(const float* emit, const float* trans, const int32_t
     if (!aligned_to(tags, 4) || (best_score && !aligned_to(best_score, 4))) return LCCRF_EALIGN;
     const MaxWorkspace w = max_workspace(B, N, T);
     char* base = static_cast<char*>(workspace);
+    if (scan_pays_max(B, N, T)) {
+        hipStream_t st = static_cast<hipStream_t>(stream);
+        int32_t* pin = reinterpret_cast<int32_t*>(base + w.pin);
+        hipError_t e = lccrf::launch_scan_pins(
+            LCCRF_F32, nullptr, lengths, B, N, T, scan_chunk(B, N, T), reinterpret_cast<double*>(base + w.Mx),
+            reinterpret_cast<uint8_t*>(base + w.K), pin,
+            {reinterpret_cast<double*>(base + w.Mx2), reinterpret_cast<uint8_t*>(base + w.K2),
+             reinterpret_cast<int32_t*>(base + w.pin2)},
+            best_score, st, emit, trans);
+        if (e == hipSuccess)
+            e = lccrf::launch_chunked_max(LCCRF_F32, nullptr, lengths, B, N, T, reinterpret_cast<uint8_t*>(base + w.bp),
+                                          reinterpret_cast<double*>(base + w.mid), tags, scan_chunk(B, N, T), pin, st,
+                                          emit, trans);
+        return e == hipSuccess ? LCCRF_OK : LCCRF_ELAUNCH;
+    }
     const hipError_t e = lccrf::launch_structured_max(emit, trans, lengths, B, N, T,
                                                       reinterpret_cast<uint8_t*>(base + w.bp),
                                                       reinterpret_cast<double*>(base + w.mid), best_score, tags,

@@ -787,7 +787,7 @@ static hipError_t launch_geo(int op, ChainArgs a, hipStream_t st, hipEvent_t bet
 // Structured potentials at 32 < T <= 128 (G: the geometry of the dense kernels for that tag count).
 template <typename G, bool ALIGNED, int PF2>
 static hipError_t launch_structured_geo(int op, const ChainArgs& a, hipStream_t st, hipEvent_t between) {
-    hipLaunchKernelGGL((chain_half_kernel<G, float, ALIGNED, 4, true>), dim3(2 * a.B), dim3(G::W), 0, st, a);
+    hipLaunchKernelGGL((chain_half_kernel<G, float, ALIGNED, 4, true>), dim3(2 * a.B * a.C), dim3(G::W), 0, st, a);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     if (between) {
@@ -798,7 +798,7 @@ static hipError_t launch_structured_geo(int op, const ChainArgs& a, hipStream_t 
         hipLaunchKernelGGL(logz_combine_kernel, dim3(a.B), dim3(64), 0, st, a);
         return hipGetLastError();
     }
-    hipLaunchKernelGGL((chain_marginal_kernel<G, float, ALIGNED, PF2, true>), dim3(2 * a.B), dim3(G::W), 0, st, a);
+    hipLaunchKernelGGL((chain_marginal_kernel<G, float, ALIGNED, PF2, true>), dim3(2 * a.B * a.C), dim3(G::W), 0, st, a);
     return hipGetLastError();
 }
 template <bool ALIGNED>
@@ -923,13 +923,20 @@ hipError_t launch_chunked_marginals(int dtype, const void* phi, const int32_t* l
                                     float* ua, float* ub, double* Oa, double* Ob, float* mu, int chunk,
                                     const float* Fv, const double* OF, const float* Gv, const double* OG,
                                     hipStream_t st, hipEvent_t between, bool exact_only, float* ent, const void* psi,
-                                    bool difference) {
+                                    bool difference, const float* emit, const float* trans) {
     const int C = (N + chunk - 1) / chunk;
     ChainArgs a{phi, lengths, B, N, T, ua, ub, Oa, Ob, nullptr, mu, exact_only ? 1 : 0, nullptr, chunk, C, Fv, OF, Gv, OG};
     a.ent = ent;  // entropy or expectation mode of the second pass (one-wave kernels only: the scan's tag sets)
     a.ent_kind = !ent ? 0 : !psi ? 1 : difference ? 3 : 2;
     if (ent) a.psi = psi;  // (only the second pass of the one-wave kernels looks at it)
     if (ent && !wave_supported(T)) return hipErrorInvalidValue;
+    if (emit) {  // structured potentials: the two passes as separate launches, T <= 64 (the scan's tag sets)
+        if (ent || dtype != 0 || !trans || T > 64) return hipErrorInvalidValue;
+        a.emit = emit;
+        a.trans = trans;
+        if (wave_supported(T)) return launch_wave(1, dtype, a, st, between);
+        return (T % 4) == 0 ? launch_structured_sum<true>(1, a, st, between) : launch_structured_sum<false>(1, a, st, between);
+    }
     if (wave_supported(T) && wave_chunks_fused(chunk)) {
         if (between) {  // (the boundary phases lie before it, both passes of the chunks after it)
             const hipError_t e = hipEventRecord(between, st);

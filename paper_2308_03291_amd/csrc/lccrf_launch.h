@@ -69,7 +69,8 @@ struct ScanGroupBuffers {
 hipError_t launch_scan_boundaries(int dtype, const void* phi, const int32_t* lengths, int B, int N, int T, int chunk,
                                   float* Pl, float* rel, double* base, float* Fv, double* OF, float* Gv, double* OG,
                                   const ScanGroupBuffers& gb, float* logZ, bool with_beta, hipStream_t st,
-                                  double* logZ64 = nullptr);
+                                  double* logZ64 = nullptr, const float* emit = nullptr, const float* trans = nullptr);
+// emit non-null: structured potentials trans + emit (dtype 0; phi is not read), here and in the launchers below.
 
 // log p(y) = score(y) - logZ for one tag path per sequence (lccrf_extras.hip); logZ64: [B] doubles
 // already computed on the same stream.
@@ -80,7 +81,8 @@ hipError_t launch_chunked_marginals(int dtype, const void* phi, const int32_t* l
                                     float* ua, float* ub, double* Oa, double* Ob, float* mu, int chunk,
                                     const float* Fv, const double* OF, const float* Gv, const double* OG,
                                     hipStream_t st, hipEvent_t between, bool exact_only, float* ent = nullptr,
-                                    const void* psi = nullptr, bool difference = false);
+                                    const void* psi = nullptr, bool difference = false, const float* emit = nullptr,
+                                    const float* trans = nullptr);
 // ent non-null (T <= 32): the second pass writes no marginals (mu may be null) but the summed conditional
 // entropies of every chunk's edges, [B][C][2] floats (base 2); launch_entropy_reduce adds them up to H [B].
 // logZ: [B] floats from the boundary pass of the same run (-inf: no finite path, H is NaN).
@@ -112,11 +114,12 @@ struct MaxGroupBuffers {  // group level of the max-plus scan ([B][G]; many chun
 };
 hipError_t launch_scan_pins(int dtype, const void* phi, const int32_t* lengths, int B, int N, int T, int chunk,
                             double* Mx, uint8_t* K, int32_t* pin, const MaxGroupBuffers& gb, float* best_score,
-                            hipStream_t st);
+                            hipStream_t st, const float* emit = nullptr, const float* trans = nullptr);
 // Best path inside every chunk between those pinned tags (lccrf_viterbi.hip);
 // mid: viterbi_mid_doubles(B, C, T) doubles of scratch.
 hipError_t launch_chunked_max(int dtype, const void* phi, const int32_t* lengths, int B, int N, int T, uint8_t* bp,
-                              double* mid, int32_t* tags, int chunk, const int32_t* pin, hipStream_t st);
+                              double* mid, int32_t* tags, int chunk, const int32_t* pin, hipStream_t st,
+                              const float* emit = nullptr, const float* trans = nullptr);
 
 // Entropy H(p) [B] in one read of phi (lccrf_extras.hip, one-wave kernels for T <= 32).  ua / ub / Oa / Ob
 // as for launch_sequential_sum (only the rows of the meeting positions are written); ha, hb: [B][T] floats.

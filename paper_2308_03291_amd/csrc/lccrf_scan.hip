@@ -74,6 +74,9 @@ struct ScanArgs {
     const double* OFin;
     const float* Gin;
     const double* OGin;
+    // Structured potentials (emit non-null; phi is then not read): phi[b][i][s][t] = trans[s][t] + emit[b][i][t].
+    const float* emit;   // [B][N][T]
+    const float* trans;  // [T][T]
 };
 
 // First and last position whose matrix belongs to chunk c (first > last: none).
@@ -234,6 +237,49 @@ struct PotentialMatrices {  // the potentials phi_i of one sequence
     }
     __device__ __forceinline__ float entry(int i, int r, int t) const {  // one entry, straight from memory
         return (r < T && t < T) ? Elem<TIN>::get(phib + (size_t)i * TT + r * T + t) * kLog2e : LCCRF_NEG_INF;
+    }
+    __device__ __forceinline__ double offset(int) const { return 0.0; }
+};
+
+// The same matrices from structured potentials, phi_i[s][t] = trans[s][t] + emit_i[t]: the transition entries of a
+// lane stay in registers (in base-2 logarithms, -inf outside T x T) and a position brings the emissions of the lane's
+// NB columns.
+template <int TP, bool F64>
+struct StructuredMatrices {
+    using S = ScanShape<TP, F64>;
+    static constexpr int NB = S::NB;
+    static constexpr int PF = 4;
+    struct Slot { float em[NB]; };
+    static constexpr bool kPaddingIsFinite = false;  // entries outside T x T are handed out as -inf
+    const float* emb;
+    const float* trans;
+    int T;
+    float tr[S::NE];
+    int coff[NB];
+    __device__ StructuredMatrices(const float* emit_b, const float* trans_, int T_, int lane) : emb(emit_b), trans(trans_), T(T_) {
+#pragma unroll
+        for (int e = 0; e < S::NE; ++e) {
+            const int s = S::row(lane, e), t = S::col(lane, e);
+            tr[e] = (s < T && t < T) ? trans[s * T + t] * kLog2e : LCCRF_NEG_INF;
+        }
+#pragma unroll
+        for (int tb = 0; tb < NB; ++tb) {
+            const int t = S::col(lane, 4 * tb);
+            coff[tb] = t < T ? t : T - 1;
+        }
+    }
+    __device__ __forceinline__ void load(int i, Slot& sl) const {
+        const float* m = emb + (size_t)i * T;
+#pragma unroll
+        for (int tb = 0; tb < NB; ++tb) sl.em[tb] = m[coff[tb]];
+    }
+    __device__ __forceinline__ double entries(const Slot& sl, float (&x)[S::NE]) const {
+#pragma unroll
+        for (int e = 0; e < S::NE; ++e) x[e] = tr[e] + sl.em[(e / 4) % NB] * kLog2e;
+        return 0.0;
+    }
+    __device__ __forceinline__ float entry(int i, int r, int t) const {
+        return (r < T && t < T) ? (trans[r * T + t] + emb[(size_t)i * T + t]) * kLog2e : LCCRF_NEG_INF;
     }
     __device__ __forceinline__ double offset(int) const { return 0.0; }
 };
@@ -609,7 +655,7 @@ __device__ __forceinline__ void exact_product(const Src& src, int first, int las
 }
 
 // One wave (up to 32 tags) or NB waves per chunk: the product of the chunk's potentials.
-template <typename TIN, int TP, bool VEC>
+template <typename TIN, int TP, bool VEC, bool STRUCT = false>
 __global__ __launch_bounds__(64 * ScanShape<TP>::NW) void chunk_product_kernel(ScanArgs a) {
     __shared__ float Pc[TP][TP + 1];
     __shared__ float Ph[TP][TP + 1];
@@ -620,11 +666,22 @@ __global__ __launch_bounds__(64 * ScanShape<TP>::NW) void chunk_product_kernel(S
     if (c * a.chunk >= L) return;
     int first, last;
     chunk_range(c, a.chunk, L, first, last);
-    const TIN* phib = static_cast<const TIN*>(a.phi) + (size_t)b * N * T * T;
     const size_t bc = (size_t)b * a.C + c;
     float* Pout = a.Pl + bc * TP * TP;
     float* rel_out = a.rel + bc * TP;
     const int lane = threadIdx.x & 63;
+    if constexpr (STRUCT) {
+        const float* emb = a.emit + (size_t)b * N * T;
+        if constexpr (kSingleFirst<TP>) {
+            const StructuredMatrices<TP, false> src(emb, a.trans, T, lane);
+            if (linear_product<TP, false>(src, first, last, T, Pout, rel_out, a.base + bc, shared)) return;
+        }
+        const StructuredMatrices<TP, true> src(emb, a.trans, T, lane);
+        if (linear_product<TP, true>(src, first, last, T, Pout, rel_out, a.base + bc, shared)) return;
+        exact_product<TP>(src, first, last, T, Pout, rel_out, a.base + bc, Pc, Ph);
+        return;
+    }
+    const TIN* phib = static_cast<const TIN*>(a.phi) + (size_t)b * N * T * T;
     if constexpr (kSingleFirst<TP>) {
         const PotentialMatrices<TIN, TP, false, VEC> src(phib, T, lane);
         if (linear_product<TP, false>(src, first, last, T, Pout, rel_out, a.base + bc, shared)) return;
@@ -710,7 +767,8 @@ __global__ __launch_bounds__(64) void chunk_boundary_kernel(ScanArgs a) {
         float nv;  // alpha before chunk c0, entry o in lanes LPRow o ..
         if (c0 == 0) {
             const TIN* phib = static_cast<const TIN*>(a.phi) + (size_t)b * N * T * T;
-            const float v = (lane < T) ? Elem<TIN>::get(phib + lane) * kLog2e : LCCRF_NEG_INF;  // alpha_0
+            const float v = lane >= T ? LCCRF_NEG_INF  // alpha_0
+                            : (a.emit ? a.trans[lane] + a.emit[(size_t)b * N * T + lane] : Elem<TIN>::get(phib + lane)) * kLog2e;
             const float d = finite_or_zero(xor_max<1, 64>(v));
             O = (double)d;
             nv = (o < T) ? __shfl(v, o, 64) - d : LCCRF_NEG_INF;
@@ -812,6 +870,9 @@ struct MaxScanArgs {
     int GS, G;
     double* Mx2;
     const int32_t* pin_in;
+    // Structured potentials (emit non-null; phi is then not read), as in ScanArgs.
+    const float* emit;
+    const float* trans;
 };
 
 // A double of lane `K` of every aligned group of four lanes.
@@ -869,7 +930,7 @@ __device__ __forceinline__ void maxplus_product(int first, int last, int T, doub
 struct MaxSlotF { float x[4]; };
 struct MaxSlotD { double x[4]; };
 
-template <typename TIN>
+template <typename TIN, bool STRUCT = false>
 __global__ __launch_bounds__(64) void chunk_maxplus_kernel(MaxScanArgs a) {
     __shared__ __attribute__((aligned(16))) float Xs[2][16][16];
     const int lane = threadIdx.x, r = lane >> 2, q = lane & 3;
@@ -880,7 +941,6 @@ __global__ __launch_bounds__(64) void chunk_maxplus_kernel(MaxScanArgs a) {
     int first, last;
     chunk_range(c, a.chunk, L, first, last);
     const size_t TT = (size_t)T * T;
-    const TIN* phib = static_cast<const TIN*>(a.phi) + (size_t)b * N * TT;
     int off[4];
     bool in[4];
 #pragma unroll
@@ -889,6 +949,27 @@ __global__ __launch_bounds__(64) void chunk_maxplus_kernel(MaxScanArgs a) {
         in[jj] = r < T && t < T;
         off[jj] = (r < T ? r : T - 1) * T + (t < T ? t : T - 1);
     }
+    if constexpr (STRUCT) {
+        // the candidates are the single-precision sums trans + emit, as the materialised tensor would hold them
+        const float* emb = a.emit + (size_t)b * N * T;
+        float tr[4];
+        int col[4];
+#pragma unroll
+        for (int jj = 0; jj < 4; ++jj) {
+            tr[jj] = a.trans[off[jj]];
+            col[jj] = 4 * q + jj < T ? 4 * q + jj : T - 1;
+        }
+        maxplus_product<kScanPF, MaxSlotF, float>(
+            first, last, T, a.Mx + ((size_t)b * a.C + c) * 256,
+            [&](int i, MaxSlotF& sl) {
+                const float* m = emb + (size_t)i * T;
+#pragma unroll
+                for (int jj = 0; jj < 4; ++jj) sl.x[jj] = m[col[jj]];
+            },
+            [&](const MaxSlotF& sl, int jj) { return in[jj] ? tr[jj] + sl.x[jj] : LCCRF_NEG_INF; }, Xs);
+        return;
+    }
+    const TIN* phib = static_cast<const TIN*>(a.phi) + (size_t)b * N * TT;
     maxplus_product<kScanPF, MaxSlotF, float>(
         first, last, T, a.Mx + ((size_t)b * a.C + c) * 256,
         [&](int i, MaxSlotF& sl) {
@@ -949,7 +1030,8 @@ __global__ __launch_bounds__(64) void chunk_maxplus_boundary_kernel(MaxScanArgs 
     double dv;
     if (c0 == 0) {
         const TIN* phib = static_cast<const TIN*>(a.phi) + (size_t)b * N * T * T;
-        dv = (t < T) ? (double)Elem<TIN>::get(phib + t) : ninf;  // delta_0
+        dv = t >= T ? ninf  // delta_0
+             : a.emit ? (double)(a.trans[t] + a.emit[(size_t)b * N * T + t]) : (double)Elem<TIN>::get(phib + t);
     } else {
         dv = (t == a.pin_in[bg + g - 1]) ? 0.0 : ninf;  // the tag fixed at the end of the group before
     }
@@ -1042,7 +1124,9 @@ static hipError_t launch_scan_boundaries_t(ScanArgs a, const ScanGroupBuffers& g
     // vector loads of a lane's NB neighbouring columns: T a multiple of NB, and the rows aligned for them
     constexpr int NB = ScanShape<TP>::NB;
     const bool vec = NB > 1 && a.T % NB == 0 && (NB == 3 ? sizeof(TIN) == 4 : true);
-    if (vec)
+    if (a.emit)
+        hipLaunchKernelGGL((chunk_product_kernel<float, TP, false, true>), dim3(a.B * a.C), dim3(kProductThreads), 0, st, a);
+    else if (vec)
         hipLaunchKernelGGL((chunk_product_kernel<TIN, TP, true>), dim3(a.B * a.C), dim3(kProductThreads), 0, st, a);
     else
         hipLaunchKernelGGL((chunk_product_kernel<TIN, TP, false>), dim3(a.B * a.C), dim3(kProductThreads), 0, st, a);
@@ -1076,10 +1160,11 @@ static hipError_t launch_scan_boundaries_t(ScanArgs a, const ScanGroupBuffers& g
 hipError_t launch_scan_boundaries(int dtype, const void* phi, const int32_t* lengths, int B, int N, int T, int chunk,
                                   float* Pl, float* rel, double* base, float* Fv, double* OF, float* Gv, double* OG,
                                   const ScanGroupBuffers& gb, float* logZ, bool with_beta, hipStream_t st,
-                                  double* logZ64) {
+                                  double* logZ64, const float* emit, const float* trans) {
     const int C = (N + chunk - 1) / chunk;
     ScanArgs a{phi, lengths, B, N, T, chunk, C, Pl, rel, base, Fv, OF, Gv, OG, logZ, with_beta ? 1 : 0, logZ64,
-               0, 1, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr};
+               0, 1, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, emit, trans};
+    if (emit && (dtype != 0 || !trans)) return hipErrorInvalidValue;
     if (T <= 16)
         return dtype == 0 ? launch_scan_boundaries_t<float, 16>(a, gb, st) : launch_scan_boundaries_t<uint16_t, 16>(a, gb, st);
     if (T <= 32)
@@ -1094,7 +1179,8 @@ hipError_t launch_scan_boundaries(int dtype, const void* phi, const int32_t* len
 
 template <typename TIN>
 static hipError_t launch_scan_pins_t(MaxScanArgs a, const MaxGroupBuffers& gb, hipStream_t st) {
-    hipLaunchKernelGGL(chunk_maxplus_kernel<TIN>, dim3(a.B * a.C), dim3(64), 0, st, a);
+    if (a.emit) hipLaunchKernelGGL((chunk_maxplus_kernel<float, true>), dim3(a.B * a.C), dim3(64), 0, st, a);
+    else hipLaunchKernelGGL(chunk_maxplus_kernel<TIN>, dim3(a.B * a.C), dim3(64), 0, st, a);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     const int gs = scan_group_size(a.C);
@@ -1121,9 +1207,10 @@ static hipError_t launch_scan_pins_t(MaxScanArgs a, const MaxGroupBuffers& gb, h
 
 hipError_t launch_scan_pins(int dtype, const void* phi, const int32_t* lengths, int B, int N, int T, int chunk,
                             double* Mx, uint8_t* K, int32_t* pin, const MaxGroupBuffers& gb, float* best_score,
-                            hipStream_t st) {
+                            hipStream_t st, const float* emit, const float* trans) {
     const int C = (N + chunk - 1) / chunk;
-    MaxScanArgs a{phi, lengths, B, N, T, chunk, C, Mx, K, pin, best_score, 0, 1, nullptr, nullptr};
+    MaxScanArgs a{phi, lengths, B, N, T, chunk, C, Mx, K, pin, best_score, 0, 1, nullptr, nullptr, emit, trans};
+    if (emit && (dtype != 0 || !trans)) return hipErrorInvalidValue;
     return dtype == 0 ? launch_scan_pins_t<float>(a, gb, st) : launch_scan_pins_t<uint16_t>(a, gb, st);
 }
 

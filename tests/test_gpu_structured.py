@@ -97,3 +97,67 @@ def test_structured_needs_a_supported_tag_set(crf):
     emit, trans = _make(7300, 2, 6, 129)
     with pytest.raises(crf.LccrfError, match="not available"):
         crf.lccrf_log_partition_structured(emit.cuda(), trans.cuda())
+
+
+@pytest.fixture
+def chunk(crf):
+    """Sets the scan's chunk size for one test and restores the default afterwards."""
+    yield crf.set_scan_chunk
+    crf.set_scan_chunk(0)
+
+
+def _scan_lens(N, k):
+    cand = [0, 1, 2, k - 1, k, k + 1, 2 * k + 1, N - 1, N]
+    return torch.tensor([min(max(c, 0), N) for c in cand], dtype=torch.int32)
+
+
+@pytest.mark.parametrize("k", [0, 4, 7])
+@pytest.mark.parametrize("T,N", [(1, 70), (5, 130), (13, 257), (16, 300), (17, 90), (32, 140), (33, 64), (45, 100),
+                                 (48, 96), (64, 130), (63, 71)])
+def test_structured_under_the_scan(crf, oracle_mod, chunk, T, N, k):
+    """Long chains in small batches: the structured calls take the chunked scan (sum queries up to 64 tags, the argmax
+    up to 16) whenever the dense call of the same shape would, with the chunk's potentials formed from the transition
+    entries in registers and the streamed emissions."""
+    chunk(k)
+    lens = _scan_lens(N, k or 8)
+    B = len(lens)
+    assert crf.auto_algo(crf.OP_MARGINALS, B, N, T) == crf.ALGO_SCAN
+    assert crf.auto_algo(crf.OP_ARGMAX, B, N, T) == (crf.ALGO_SCAN if T <= 16 and N >= 16 * (k or 8) else crf.ALGO_SEQUENTIAL)
+    emit, trans = _make(7400 + 13 * T + N + k, B, N, T)
+    _check(crf, oracle_mod, emit, trans, lens, f"structured scan T={T} N={N} k={k}")
+
+
+@pytest.mark.parametrize("T,N,k", [(8, 1100, 16), (16, 2100, 8), (30, 700, 8)])
+def test_structured_scan_many_chunks(crf, oracle_mod, chunk, T, N, k):
+    """64 chunks or more a sequence: the boundary phase itself runs over groups of chunks."""
+    chunk(k)
+    lens = torch.tensor([N, N - 3, N // 2 + 1, 1], dtype=torch.int32)
+    assert crf.auto_algo(crf.OP_MARGINALS, 4, N, T) == crf.ALGO_SCAN
+    emit, trans = _make(7500 + T, 4, N, T, scale_e=1.0, scale_t=0.7)
+    _check(crf, oracle_mod, emit, trans, lens, f"structured scan, many chunks, T={T} N={N} k={k}")
+
+
+@pytest.mark.parametrize("T,N", [(9, 200), (16, 160), (24, 100), (40, 80)])
+def test_structured_scan_with_forbidden_transitions_and_peaked_emissions(crf, oracle_mod, T, N):
+    """-inf transitions (the zero pattern of the chunk products) and emissions of scale 12 (the single-precision
+    product gives up, the double-precision one or the exact one takes over)."""
+    assert crf.auto_algo(crf.OP_MARGINALS, 3, N, T) == crf.ALGO_SCAN
+    emit, trans = _make(7600 + T, 3, N, T, scale_e=12.0, scale_t=3.0)
+    trans[0, 2] = trans[1, 0] = trans[3, 2] = float("-inf")
+    trans[:, T - 1] = float("-inf")
+    trans[T - 1, T - 1] = 0.0
+    lens = torch.tensor([N, N - 1, 37], dtype=torch.int32)
+    _check(crf, oracle_mod, emit, trans, lens, f"structured scan with -inf, T={T}")
+
+
+def test_structured_scan_agrees_with_dense_scan(crf):
+    emit, trans = _make(7700, 4, 512, 16)
+    assert crf.auto_algo(crf.OP_ARGMAX, 4, 512, 16) == crf.ALGO_SCAN
+    phi = (emit[:, :, None, :] + trans[None, None]).contiguous().cuda()
+    lz_a, mu_a = crf.lccrf_marginals_structured(emit.cuda(), trans.cuda())
+    lz_b, mu_b = crf.lccrf_marginals(phi)
+    assert torch.allclose(lz_a, lz_b, rtol=2e-6, atol=0)
+    assert float((mu_a - mu_b).abs().max()) < 5e-6
+    s_a, y_a = crf.lccrf_argmax_structured(emit.cuda(), trans.cuda())
+    s_b, y_b = crf.lccrf_argmax(phi)
+    assert torch.equal(y_a, y_b) and torch.equal(s_a, s_b)
