@@ -30,13 +30,13 @@ __device__ __forceinline__ void smem_init(ChainSmem<G>& sm, int tid) {
 // Normaliser of the vector in rvec[buf]: its maximum (0 if the vector is all -inf).
 template <typename G>
 __device__ __forceinline__ float read_shift(const ChainSmem<G>& sm, int buf) {
-    float d = LCCRF_NEG_INF;
-#pragma unroll
-    for (int w = 0; w < 16; w += 4) {
-        const float4 q = *reinterpret_cast<const float4*>(&sm.wmax[buf][w]);
-        d = fmaxf(fmaxf(d, fmaxf(q.x, q.y)), fmaxf(q.z, q.w));
-    }
-    return finite_or_zero(d);
+    const float4 q0 = *reinterpret_cast<const float4*>(&sm.wmax[buf][0]);
+    const float4 q1 = *reinterpret_cast<const float4*>(&sm.wmax[buf][4]);
+    const float4 q2 = *reinterpret_cast<const float4*>(&sm.wmax[buf][8]);
+    const float4 q3 = *reinterpret_cast<const float4*>(&sm.wmax[buf][12]);
+    const float a = max3_raw(max3_raw(q0.x, q0.y, q0.z), q0.w, q1.x), b = max3_raw(max3_raw(q1.y, q1.z, q1.w), q2.x, q2.y);
+    const float c = max3_raw(max3_raw(q2.z, q2.w, q3.x), q3.y, q3.z);
+    return finite_or_zero(max3_raw(max3_raw(a, b, c), q3.w, q3.w));
 }
 
 // -log2 of the sum of the marginals the last step wrote (0 if nothing usable was written).

@@ -217,6 +217,33 @@ __device__ __forceinline__ double lane_xor(double x) {
     return __longlong_as_double(((long long)hi << 32) | (unsigned int)lo);
 }
 
+// Maxima as the bare instructions.  In front of a max whose operand comes from memory or from another lane the
+// compiler puts a canonicalising copy of that operand (it cannot rule out a signalling NaN), which also keeps the
+// cross-lane move from folding into the max: three instructions where one does.  NaN operands are ignored in favour
+// of the others, as by fmaxf.  The DPP form waits out the two states a vector result needs before a DPP read.
+__device__ __forceinline__ float max3_raw(float a, float b, float c) {
+    float r;
+    asm("v_max3_f32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
+    return r;
+}
+template <int CTRL>
+__device__ __forceinline__ float max_with_dpp(float x) {  // max(x, value of the lane CTRL names); all lanes active
+    float r;
+    static_assert(CTRL == kDppQuadXor1 || CTRL == kDppQuadXor2 || CTRL == kDppHalfMirror || CTRL == kDppRowRor4 ||
+                      CTRL == kDppRowRor8, "one of the lane patterns above");
+    if constexpr (CTRL == kDppQuadXor1)
+        asm("s_nop 1\n\tv_max_f32_dpp %0, %1, %1 quad_perm:[1,0,3,2] row_mask:0xf bank_mask:0xf" : "=v"(r) : "v"(x));
+    else if constexpr (CTRL == kDppQuadXor2)
+        asm("s_nop 1\n\tv_max_f32_dpp %0, %1, %1 quad_perm:[2,3,0,1] row_mask:0xf bank_mask:0xf" : "=v"(r) : "v"(x));
+    else if constexpr (CTRL == kDppHalfMirror)
+        asm("s_nop 1\n\tv_max_f32_dpp %0, %1, %1 row_half_mirror row_mask:0xf bank_mask:0xf" : "=v"(r) : "v"(x));
+    else if constexpr (CTRL == kDppRowRor4)
+        asm("s_nop 1\n\tv_max_f32_dpp %0, %1, %1 row_ror:4 row_mask:0xf bank_mask:0xf" : "=v"(r) : "v"(x));
+    else
+        asm("s_nop 1\n\tv_max_f32_dpp %0, %1, %1 row_ror:8 row_mask:0xf bank_mask:0xf" : "=v"(r) : "v"(x));
+    return r;
+}
+
 // All-reduce over the lanes of a wave whose ids differ only in the bits [LO, HI) (LO, HI
 // powers of two, LO >= HI means a single lane: nothing to do).  Every lane of a group ends
 // with the bit-identical result (both partners of an exchange add the same two numbers).
@@ -225,17 +252,24 @@ __device__ __forceinline__ double lane_xor(double x) {
 // and holds that quad's value): a DPP move instead of a trip through the LDS crossbar.
 template <int LO, int HI>
 __device__ __forceinline__ float xor_max(float x) {
+#ifdef LCCRF_LANE_EXCHANGE_CLASSIC
     if (LO <= 1 && 1 < HI) x = fmaxf(x, dpp<kDppQuadXor1>(x));
     if (LO <= 2 && 2 < HI) x = fmaxf(x, dpp<kDppQuadXor2>(x));
-    if (LO <= 4 && 4 < HI) x = fmaxf(x, (LO <= 1 && !kNoMirror) ? dpp<kDppHalfMirror>(x) : lane_xor<4>(x));
+    if (LO <= 4 && 4 < HI) x = fmaxf(x, lane_xor<4>(x));
     if (LO <= 8 && 8 < HI) x = fmaxf(x, dpp<kDppRowRor8>(x));
+#else
+    if (LO <= 1 && 1 < HI) x = max_with_dpp<kDppQuadXor1>(x);
+    if (LO <= 2 && 2 < HI) x = max_with_dpp<kDppQuadXor2>(x);
+    if (LO <= 4 && 4 < HI) x = (LO <= 1) ? max_with_dpp<kDppHalfMirror>(x) : fmaxf(x, lane_xor<4>(x));
+    if (LO <= 8 && 8 < HI) x = max_with_dpp<kDppRowRor8>(x);
+#endif
     if (LO <= 16 && 16 < HI) {  // both halves of the swapped pair: no select needed for a symmetric op
         const auto r = __builtin_amdgcn_permlane16_swap(__float_as_int(x), __float_as_int(x), false, false);
-        x = fmaxf(__int_as_float(r[0]), __int_as_float(r[1]));
+        x = max3_raw(__int_as_float(r[0]), __int_as_float(r[1]), __int_as_float(r[1]));
     }
     if (LO <= 32 && 32 < HI) {
         const auto r = __builtin_amdgcn_permlane32_swap(__float_as_int(x), __float_as_int(x), false, false);
-        x = fmaxf(__int_as_float(r[0]), __int_as_float(r[1]));
+        x = max3_raw(__int_as_float(r[0]), __int_as_float(r[1]), __int_as_float(r[1]));
     }
     return x;
 }
