@@ -124,12 +124,12 @@ static hipError_t launch_entropy_combine(const ChainArgs& a, float* H, hipStream
 // weight zero contributes nothing whatever psi holds there.  In modes 1 and 2 a common shift of
 // h (its largest finite entry) moves into a double-precision offset at every step, so the vector
 // stays small however long the chain is.
-// The entropy (mode 0) at 33 .. 128 tags first tries every step with one shift for the whole matrix, the
-// normaliser of the vector it starts from, as the chain kernels do (lccrf_chain.hip): U / S + log2 S does not
-// depend on the shift as long as no term that matters is flushed, which holds if every sum lies in
-// [2^-60, 2^60]; otherwise the step is replayed exactly on the same registers.  The other modes and
-// geometries take plain exact steps (every sum against its own maximum): the forward step takes the
-// column maxima through LDS first, then the sums.
+// At 33 .. 128 tags every mode first tries every step with one shift for the whole matrix, the normaliser
+// of the vector it starts from, as the chain kernels do (lccrf_chain.hip): U / S (+ log2 S) does not depend
+// on the shift as long as no term that matters is flushed, which holds if every sum lies in
+// [2^-60, 2^60]; otherwise the step is replayed exactly on the same registers.  The other geometries take
+// plain exact steps (every sum against its own maximum): the forward step takes the column maxima
+// through LDS first, then the sums.
 template <typename G>
 struct EntropySmem {
     alignas(16) float pmax[G::WAVES][G::TCAP];
@@ -165,7 +165,7 @@ __global__ __launch_bounds__(G::W) void entropy_half_kernel(ChainArgs a) {
     constexpr bool LATE_PSI = CROSS && G::WAVES >= 16;
     constexpr bool QRING = CROSS && !LATE_PSI;
     constexpr int QITEMS = QRING ? ITEMS : 1, QPF = QRING ? PF : 1;
-    constexpr bool SPEC = !CROSS && ITEMS == 4 && G::LPR >= 16;  // speculative step first
+    constexpr bool SPEC = (ITEMS == 4 || ITEMS == 8) && G::LPR >= 16;  // speculative step first
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int b = blockIdx.x >> 1, dir = blockIdx.x & 1;
     const int N = a.N, T = a.T;
@@ -254,12 +254,15 @@ __global__ __launch_bounds__(G::W) void entropy_half_kernel(ChainArgs a) {
 #pragma unroll
                 for (int k = 0; k < ITEMS; ++k) {
                     const float uac = ua[k] - d;
+                    float f[4] = {0.f, 0.f, 0.f, 0.f};
+                    if constexpr (CROSS) edge_term(i, slot, k, x[k], f);
 #pragma unroll
                     for (int j = 0; j < 4; ++j) {
                         const float arg = __builtin_fmaf(x[k][j], kLog2e, uac);
                         const float ex = ex2(arg);
                         ls[j] += ex;
-                        lu[j] = __builtin_fmaf(ex, hin[k] - log2_term(arg), lu[j]);
+                        if (CROSS) lu[j] += ex > 0.f ? ex * (hin[k] + f[j]) : 0.f;
+                        else lu[j] = __builtin_fmaf(ex, hin[k] - log2_term(arg), lu[j]);
                     }
                 }
 #pragma unroll
@@ -283,7 +286,7 @@ __global__ __launch_bounds__(G::W) void entropy_half_kernel(ChainArgs a) {
                         }
                         good = sum_in_range(S);
                         sm.rvec[buf ^ 1][tid] = d + lg2(S);
-                        sm.hvec[buf ^ 1][tid] = entropy_of(U, S);
+                        sm.hvec[buf ^ 1][tid] = CROSS ? expectation_of(U, S) : entropy_of(U, S);
                     }
                     if (!__all(good) && lane == 0) sm.bad[flag] = 1;
                 }
@@ -377,24 +380,31 @@ __global__ __launch_bounds__(G::W) void entropy_half_kernel(ChainArgs a) {
                 for (int k = 0; k < ITEMS; ++k) {
                     Sl[k] = 0.f;
                     Ul[k] = 0.f;
+                    float f[4] = {0.f, 0.f, 0.f, 0.f};
+                    if constexpr (CROSS) edge_term(i, slot, k, y[k], f);
 #pragma unroll
                     for (int j = 0; j < 4; ++j) {
                         const float arg = __builtin_fmaf(y[k][j], kLog2e, ub[j] - d);
                         const float ex = ex2(arg);
                         Sl[k] += ex;
-                        Ul[k] = __builtin_fmaf(ex, hin[j] - log2_term(arg), Ul[k]);
+                        if (CROSS) Ul[k] += ex > 0.f ? ex * (hin[j] + f[j]) : 0.f;
+                        else Ul[k] = __builtin_fmaf(ex, hin[j] - log2_term(arg), Ul[k]);
                     }
                 }
                 // four rows at a time: each lane ends up with the complete sums of one of them
                 const int kk = 2 * (lane & 1) + ((lane >> 1) & 1);
-                const float S = reduce4_over_lanes<G::LPR>(Sl[0], Sl[1], Sl[2], Sl[3], lane);
-                const float U = reduce4_over_lanes<G::LPR>(Ul[0], Ul[1], Ul[2], Ul[3], lane);
-                const int s = r0 + kk * G::RPP;
-                if ((tid % G::LPR) < 4 && s < T) {
-                    sm.rvec[buf ^ 1][s] = d + lg2(S);
-                    sm.hvec[buf ^ 1][s] = entropy_of(U, S);
+                bool good = true;
+#pragma unroll
+                for (int k0 = 0; k0 < ITEMS; k0 += 4) {
+                    const float S = reduce4_over_lanes<G::LPR>(Sl[k0], Sl[k0 + 1], Sl[k0 + 2], Sl[k0 + 3], lane);
+                    const float U = reduce4_over_lanes<G::LPR>(Ul[k0], Ul[k0 + 1], Ul[k0 + 2], Ul[k0 + 3], lane);
+                    const int s = r0 + (k0 + kk) * G::RPP;
+                    if ((tid % G::LPR) < 4 && s < T) {
+                        sm.rvec[buf ^ 1][s] = d + lg2(S);
+                        sm.hvec[buf ^ 1][s] = CROSS ? expectation_of(U, S) : entropy_of(U, S);
+                    }
+                    good = good && (s >= T || sum_in_range(S));
                 }
-                const bool good = s >= T || sum_in_range(S);
                 if (!__all(good) && lane == 0) sm.bad[flag] = 1;
                 __syncthreads();
                 ++nstep;
