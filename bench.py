@@ -98,6 +98,7 @@ def cpu_baseline(w, budget_s: float = 20.0):
         reps += 1
     pots = nseq * w.N * w.T * w.T
     return {"value": reps * pots / dt, "unit": "potentials/s", "cores": cores, "kind": "oracle",
+            "single_thread_value": 1.0 / per_pot,  # the calibration pass: one sequence (a prefix of it), one thread
             "sample": f"fp64 oracle marginals on the first {nseq} of {w.B} sequences of {w.key} "
                       f"({pots} potentials a pass, {reps} passes, {dt:.2f} s wall, OpenMP over sequences)"}
 
