@@ -105,6 +105,9 @@ bool wave_chunks_fused(int chunk);
 // marginals exactly as launch_wave_pass.
 bool stream_supported(int T);
 hipError_t launch_stream_pass(bool second_pass, int dtype, const ChainArgs& a, hipStream_t st);
+// The first pass in an expectation mode at those tag counts (0: entropy, a.ha / a.hb; 1: cross-entropy,
+// 2: KL divergence, with a.psi and a.hoff), leaving what entropy_half_kernel leaves (lccrf_extras.hip).
+hipError_t launch_stream_expect(int mode, int dtype, const ChainArgs& a, hipStream_t st);
 hipError_t launch_wave_chunks(int dtype, const ChainArgs& a, hipStream_t st);
 
 }  // namespace lccrf

@@ -468,11 +468,12 @@ static hipError_t launch_entropy_T(const ChainArgs& a, hipStream_t st) {
         else  // two tiles in flight: eight waves, so that a thread has the registers for both rings
             hipLaunchKernelGGL((entropy_half_kernel<Geo<32, 8, 8>, TIN, ALIGNED, MODE>), grid, dim3(512), 0, st, a);
     } else
-        hipLaunchKernelGGL((entropy_half_kernel<Geo<64, 16, 16>, TIN, ALIGNED, MODE>), grid, dim3(1024), 0, st, a);
+        return hipErrorInvalidValue;  // larger tag sets take the row-batch kernel (launch_stream_expect)
     return hipGetLastError();
 }
 template <int MODE>
 static hipError_t launch_entropy_mode(int dtype, const ChainArgs& a, hipStream_t st) {
+    if (stream_supported(a.T)) return launch_stream_expect(MODE, dtype, a, st);
     const bool aligned = (a.T % 4) == 0;
     if (dtype == 0) return aligned ? launch_entropy_T<float, true, MODE>(a, st) : launch_entropy_T<float, false, MODE>(a, st);
     return aligned ? launch_entropy_T<uint16_t, true, MODE>(a, st) : launch_entropy_T<uint16_t, false, MODE>(a, st);

@@ -154,3 +154,34 @@ def test_entropy_at_config4_full_size(crf, oracle_mod):
     want_lz = oracle_mod.log_partition(phi_pick, None)
     tol = 1e-5 * np.maximum(1.0, np.maximum(np.abs(want_lz), np.abs(want_lp + want_lz)))
     assert np.all(np.abs(lp[pick] - want_lp) <= tol), f"{lp[pick]} vs {want_lp}"
+
+
+@pytest.mark.parametrize("T,N", [(129, 9), (130, 17), (192, 33), (200, 40), (255, 12), (256, 70)])
+def test_entropy_largest_tag_sets(crf, oracle_mod, T, N):
+    """129 .. 256 tags: the half chains stream every matrix in batches of 64 rows (three or four batches, ragged
+    last batch, tag counts that are not multiples of 4)."""
+    phi, lens = workloads.random_case(6500 + 13 * T + N, 4, N, T, scale=1.5, ragged=True, min_len=0)
+    _check_entropy(crf, oracle_mod, phi, lens, f"T={T} N={N}")
+
+
+@pytest.mark.parametrize("T", [160, 256])
+def test_entropy_largest_tag_sets_replays_bf16_and_forbidden_edges(crf, oracle_mod, T):
+    """Scale jumps between positions (the speculative step is rejected and the matrix streamed again), bfloat16
+    potentials, -inf edges and a sequence without any finite path."""
+    phi, lens = workloads.random_case(6600 + T, 3, 24, T, scale=1.0, ragged=True, min_len=10)
+    phi[:, 5] *= 60.0
+    phi[:, 6] -= 300.0
+    phi[:, 11] += 500.0
+    phi[:, 17] *= 40.0
+    _check_entropy(crf, oracle_mod, phi, lens, f"jumps T={T}")
+    phi, lens = workloads.random_case(6700 + T, 3, 30, T, scale=5.0, ragged=True, min_len=12, dtype="bf16")
+    _check_entropy(crf, oracle_mod, phi, lens, f"peaked bf16 T={T}")
+    phi, _ = workloads.random_case(6800 + T, 4, 14, T)
+    ninf = float("-inf")
+    phi[0, :, 3, :] = ninf
+    phi[1, 10, :, 5] = ninf
+    phi[2, 12, :, :] = ninf          # no finite path: NaN on both sides
+    mask = torch.rand(14, T, T, generator=torch.Generator().manual_seed(7)) < 0.5
+    phi[3][mask] = ninf
+    phi[3, :, torch.arange(T), torch.arange(T)] = 0.0
+    _check_entropy(crf, oracle_mod, phi, None, f"-inf T={T}")

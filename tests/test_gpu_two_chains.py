@@ -151,3 +151,33 @@ def test_two_chains_argument_checks(crf):
         crf.lccrf_kl_divergence(p, p.to(torch.bfloat16))
     out = crf.lccrf_cross_entropy(p, p, torch.tensor([4, 0], dtype=torch.int32, device="cuda")).cpu().numpy()
     assert out[0] == pytest.approx(4 * math.log(3), rel=1e-6) and out[1] == 0.0
+
+
+@pytest.mark.parametrize("T,N", [(129, 9), (130, 17), (192, 33), (200, 40), (255, 12), (256, 70)])
+def test_two_chains_largest_tag_sets(crf, oracle_mod, T, N):
+    """129 .. 256 tags: both tensors stream through the half chains in batches of 64 rows."""
+    p, q, lens = _pair(7600 + 13 * T + N, 4, N, T, ragged=True, min_len=0)
+    _check(crf, oracle_mod, p, q, lens, f"T={T} N={N}")
+
+
+@pytest.mark.parametrize("T", [160, 256])
+def test_two_chains_largest_tag_sets_replays_bf16_and_forbidden_edges(crf, oracle_mod, T):
+    p, q, lens = _pair(7700 + T, 3, 24, T, scale_p=1.0, ragged=True, min_len=10)
+    p[:, 5] *= 60.0
+    p[:, 6] -= 300.0
+    p[:, 11] += 500.0
+    p[:, 17] *= 40.0
+    _check(crf, oracle_mod, p, q, lens, f"jumps T={T}")
+    p, q, lens = _pair(7800 + T, 3, 30, T, scale_p=5.0, scale_q=3.0, dtype="bf16", ragged=True, min_len=12)
+    _check(crf, oracle_mod, p, q, lens, f"peaked bf16 T={T}")
+    p, q, _ = _pair(7900 + T, 5, 14, T)
+    ninf = float("-inf")
+    p[0, :, 3, :] = ninf             # p never leaves tag 3: q's values on those edges do not matter
+    q[0, 5, 3, :] = ninf
+    q[1, 10, :, 5] = ninf            # q forbids what p allows: +inf
+    p[2, 12, :, :] = ninf            # p has no finite path: NaN
+    mask = torch.rand(14, T, T, generator=torch.Generator().manual_seed(7)) < 0.5
+    p[3][mask] = ninf
+    p[3, :, torch.arange(T), torch.arange(T)] = 0.0
+    q[4, 12, :, :] = ninf            # q has no finite path, p has
+    _check(crf, oracle_mod, p, q, None, f"-inf T={T}")
