@@ -322,29 +322,38 @@ __device__ __forceinline__ void bwd_advance(ChainSmem<G>& sm, int& buf, int& nst
 }
 
 // ---------------------------------------------------------------------------------------
-// Forward half chain for 64 < T <= 128 (T % 4 == 0) with the tile turned through LDS memory.
+// Forward half chain for 32 < T <= 128 (T % 4 == 0) with the tile turned through LDS memory.
 //
-// With rows spread over all 16 waves, the forward step has to merge 16 partial column sums
-// through LDS behind a second barrier while 14 waves wait.  Here every tile is written to LDS
-// as it arrives (coalesced rows, one position ahead of its use) and read back so that a wave
-// owns 8 complete columns: the sum over rows never leaves the wave, the step has one barrier
-// like the backward step, and the exact replay needs no cross-wave merge either.
-// Lane l of wave w holds rows (l % 32) + 32 k, k < 4, of columns 8 w + 4 (l / 32) + j, j < 4.
+// With rows spread over all waves, the forward step has to merge the waves' partial column sums
+// through LDS behind a second barrier while all but the column waves wait.  Here every tile is written
+// to LDS as it arrives (coalesced rows, one position ahead of its use) and read back so that a wave
+// owns 256 / LPR complete columns (8 of 128 with sixteen waves, 16 of 64 with four): the sum over rows
+// never leaves the wave, the step has one barrier like the backward step, and the exact replay needs
+// no cross-wave merge either.
+// Lane l of wave w holds rows (l % LPR) + LPR k, k < 4, of columns (256 / LPR) w + 4 (l / LPR) + j, j < 4.
 template <typename G, bool ALIGNED, int PF>
-constexpr bool half_turns() { return G::LPR == 32 && G::WAVES == 16 && G::ITEMS == 4 && ALIGNED && PF == 4; }
+constexpr bool half_turns() {
+    return ((G::LPR == 32 && G::WAVES == 16) || (G::LPR == 16 && G::WAVES == 4)) && G::ITEMS == 4 && ALIGNED && PF == 4;
+}
+// LDS floats of the two turned tiles of geometry G: TCAP rows of TCAP + 4 floats each (the padding keeps 16-byte
+// accesses free of bank conflicts).
+template <typename G>
+constexpr int turn_floats() { return 2 * G::TCAP * (G::TCAP + 4); }
 
 template <typename G, typename TIN, int PF>
 __device__ __forceinline__ void forward_half_turned(ChainSmem<G>& sm, float* __restrict__ tiles, const ChainArgs& a,
                                                     const Span& sp, int tid) {
-    static_assert(G::LPR == 32 && G::WAVES == 16 && G::ITEMS == 4 && PF == 4, "laid out for 1024 threads, T <= 128");
+    static_assert(G::ITEMS == 4 && PF == 4 && G::LPR * 4 == G::TCAP && G::WAVES * (256 / G::LPR) == G::TCAP,
+                  "a wave owns 256 / LPR whole columns, a lane four rows LPR apart");
+    constexpr int LPR = G::LPR, ROWS = G::TCAP, STRIDE = G::TCAP + 4;
     const int lane = tid & 63, wave = tid >> 6;
     const int b = sp.b, N = a.N, T = a.T;
     const int p0 = sp.p0, h = forward_end(a, sp.p0, sp.e);
-    const int c4 = 4 * (tid % 32), r0 = tid / 32;
+    const int c4 = 4 * (tid % LPR), r0 = tid / LPR;
     const size_t TT = (size_t)T * T, vb = (size_t)b * N;
     const TIN* phib = static_cast<const TIN*>(a.phi) + (size_t)b * N * TT;
     const bool exact_only = a.exact_only != 0;
-    const int rowl = lane & 31, colw = 8 * wave + 4 * (lane >> 5);
+    const int rowl = lane % LPR, colw = (256 / LPR) * wave + 4 * (lane / LPR);
     const int kk = 2 * (lane & 1) + ((lane >> 1) & 1);  // the column reduce4_over_lanes leaves in this lane
 
     double O = 0.0;
@@ -362,7 +371,7 @@ __device__ __forceinline__ void forward_half_turned(ChainSmem<G>& sm, float* __r
         auto to_lds = [&](int slot, int wb) {
 #pragma unroll
             for (int k = 0; k < 4; ++k)
-                *reinterpret_cast<float4*>(&tiles[(wb * 128 + r0 + 32 * k) * kTurnStride + c4]) =
+                *reinterpret_cast<float4*>(&tiles[(wb * ROWS + r0 + LPR * k) * STRIDE + c4]) =
                     make_float4(ring[slot][k][0], ring[slot][k][1], ring[slot][k][2], ring[slot][k][3]);
         };
 #pragma unroll
@@ -378,12 +387,12 @@ __device__ __forceinline__ void forward_half_turned(ChainSmem<G>& sm, float* __r
                 const int i = first + done;
                 const int rb = p & 1, nslot = (p + 1) % PF;
                 // this wave's columns of tile i, four rows at a time
-                const float* mine = &tiles[(rb * 128 + rowl) * kTurnStride + colw];
+                const float* mine = &tiles[(rb * ROWS + rowl) * STRIDE + colw];
                 const float d = read_shift<G>(sm, buf);
                 O += (double)d;
                 float ua[4];
 #pragma unroll
-                for (int k = 0; k < 4; ++k) ua[k] = sm.rvec[buf][rowl + 32 * k] - d;  // -inf for rows >= T
+                for (int k = 0; k < 4; ++k) ua[k] = sm.rvec[buf][rowl + LPR * k] - d;  // -inf for rows >= T
                 if (tid < T) a.ua[(vb + i - 1) * T + tid] = sm.rvec[buf][tid] - d;
                 if (tid == 0) a.Oa[vb + i - 1] = O;
                 // tile i + 1 goes to the other LDS buffer; its ring slot takes tile i + 1 + PF
@@ -399,17 +408,17 @@ __device__ __forceinline__ void forward_half_turned(ChainSmem<G>& sm, float* __r
 #pragma unroll
                     for (int k = 0; k < 4; ++k) {
                         const float uac = ua[k] - d;  // shift c = d, the previous normaliser
-                        const float4 q = *reinterpret_cast<const float4*>(mine + 32 * k * kTurnStride);
+                        const float4 q = *reinterpret_cast<const float4*>(mine + LPR * k * STRIDE);
                         ls[0] += ex2(__builtin_fmaf(q.x, kLog2e, uac));
                         ls[1] += ex2(__builtin_fmaf(q.y, kLog2e, uac));
                         ls[2] += ex2(__builtin_fmaf(q.z, kLog2e, uac));
                         ls[3] += ex2(__builtin_fmaf(q.w, kLog2e, uac));
                     }
-                    const float S = reduce4_over_lanes<32>(ls[0], ls[1], ls[2], ls[3], lane);
+                    const float S = reduce4_over_lanes<LPR>(ls[0], ls[1], ls[2], ls[3], lane);
                     const int col = colw + kk;
                     const float r = (col < T) ? d + lg2(S) : LCCRF_NEG_INF;
                     if (rowl < 4) sm.rvec[buf ^ 1][col] = r;
-                    const float wm = xor_max<32, 64>(xor_max<1, 4>(r));
+                    const float wm = xor_max<LPR, 64>(xor_max<1, 4>(r));
                     if (lane == 0) sm.wmax[buf ^ 1][wave] = wm;
                     const bool ok = col >= T || sum_in_range(S);
                     if (!__all(ok) && lane == 0) sm.bad[flag] = 1;
@@ -421,7 +430,7 @@ __device__ __forceinline__ void forward_half_turned(ChainSmem<G>& sm, float* __r
                     float lm[4] = {LCCRF_NEG_INF, LCCRF_NEG_INF, LCCRF_NEG_INF, LCCRF_NEG_INF};
 #pragma unroll
                     for (int k = 0; k < 4; ++k) {
-                        const float4 q = *reinterpret_cast<const float4*>(mine + 32 * k * kTurnStride);
+                        const float4 q = *reinterpret_cast<const float4*>(mine + LPR * k * STRIDE);
                         v[k][0] = __builtin_fmaf(q.x, kLog2e, ua[k]);
                         v[k][1] = __builtin_fmaf(q.y, kLog2e, ua[k]);
                         v[k][2] = __builtin_fmaf(q.z, kLog2e, ua[k]);
@@ -432,16 +441,16 @@ __device__ __forceinline__ void forward_half_turned(ChainSmem<G>& sm, float* __r
                     float r[4];
 #pragma unroll
                     for (int j = 0; j < 4; ++j) {
-                        const float M = xor_max<1, 32>(lm[j]);
+                        const float M = xor_max<1, LPR>(lm[j]);
                         const float g = finite_or_zero(M);
                         float Sl = 0.f;
 #pragma unroll
                         for (int k = 0; k < 4; ++k) Sl += ex2(v[k][j] - g);
-                        r[j] = (colw + j < T) ? M + lg2(xor_sum<1, 32>(Sl)) : LCCRF_NEG_INF;
+                        r[j] = (colw + j < T) ? M + lg2(xor_sum<1, LPR>(Sl)) : LCCRF_NEG_INF;
                     }
                     __syncthreads();  // nobody still reads the rejected vector
                     if (rowl == 0) *reinterpret_cast<float4*>(&sm.rvec[buf ^ 1][colw]) = make_float4(r[0], r[1], r[2], r[3]);
-                    const float wm = xor_max<32, 64>(fmaxf(fmaxf(r[0], r[1]), fmaxf(r[2], r[3])));
+                    const float wm = xor_max<LPR, 64>(fmaxf(fmaxf(r[0], r[1]), fmaxf(r[2], r[3])));
                     if (lane == 0) sm.wmax[buf ^ 1][wave] = wm;
                     __syncthreads();
                 }
@@ -457,6 +466,166 @@ __device__ __forceinline__ void forward_half_turned(ChainSmem<G>& sm, float* __r
     O += (double)d;
     if (tid < T) a.ua[(vb + h) * T + tid] = sm.rvec[buf][tid] - d;
     if (tid == 0) a.Oa[vb + h] = O;
+}
+
+// The forward chain of the second pass in the same turned form (four-wave geometry, 32 < T <= 64, T % 4 == 0):
+// it continues alpha past the meeting point and writes the marginals of positions h + 1 .. e.  Measured on
+// 128 ragged sequences of 48 tags this chain, with its second barrier a step, was what the second pass waited
+// for (82 us alone against 65 us for the backward chain alone).  A lane writes the marginals of its four rows
+// of four columns; the sixteen lanes of a column quad cover sixteen consecutive rows.
+template <typename G, bool ALIGNED>
+constexpr bool marginal_turns() { return G::LPR == 16 && G::WAVES == 4 && G::ITEMS == 4 && ALIGNED; }
+
+template <typename G, typename TIN>
+__device__ __forceinline__ void forward_marginal_turned(ChainSmem<G>& sm, float* __restrict__ tiles, const ChainArgs& a,
+                                                        const Span& sp, int tid, double lz2, bool feasible) {
+    constexpr int PF = 4, LPR = G::LPR, ROWS = G::TCAP, STRIDE = G::TCAP + 4;
+    static_assert(G::ITEMS == 4 && G::LPR * 4 == G::TCAP && G::WAVES * (256 / G::LPR) == G::TCAP, "as forward_half_turned");
+    const int lane = tid & 63, wave = tid >> 6;
+    const int b = sp.b, N = a.N, T = a.T;
+    const int e = sp.e, h = meeting_point(sp.p0, sp.e);
+    const int c4 = 4 * (tid % LPR), r0 = tid / LPR;
+    const size_t TT = (size_t)T * T, vb = (size_t)b * N;
+    const TIN* phib = static_cast<const TIN*>(a.phi) + (size_t)b * N * TT;
+    float* mub = a.mu + (size_t)b * N * TT;
+    const bool exact_only = a.exact_only != 0;
+    const int rowl = lane % LPR, colw = (256 / LPR) * wave + 4 * (lane / LPR);
+    const int colc = colw < T ? colw : T - 4;  // (clamped: where the stored backward vector is read)
+    const int kk = 2 * (lane & 1) + ((lane >> 1) & 1);  // the column reduce4_over_lanes leaves in this lane
+
+    double O = a.Oa[vb + h];
+    publish_columns<G>(sm, 0, tid, (tid < T) ? a.ua[(vb + h) * T + tid] : LCCRF_NEG_INF);
+    const int first = h + 1, n = e - h;  // positions first .. e
+    if (n <= 0) return;
+    float kappa = 0.f;
+    int buf = 0, nstep = 0;
+    float ring[PF][4][4], aux[PF][4];
+    double ob[PF];
+    auto load = [&](int i, int slot) { load_tile<G, TIN, true>(phib + (size_t)i * TT, T, c4, r0, ring[slot]); };
+    auto load_aux = [&](int i, int slot) {  // beta_i of this lane's columns and its offset
+        Elem<float>::get4(a.ub + (vb + i) * T + colc, aux[slot]);
+        ob[slot] = a.Ob[vb + i];
+    };
+    auto to_lds = [&](int slot, int wb) {
+#pragma unroll
+        for (int k = 0; k < 4; ++k)
+            *reinterpret_cast<float4*>(&tiles[(wb * ROWS + r0 + LPR * k) * STRIDE + c4]) =
+                make_float4(ring[slot][k][0], ring[slot][k][1], ring[slot][k][2], ring[slot][k][3]);
+    };
+#pragma unroll
+    for (int p = 0; p < PF; ++p) {
+        load(first + (p < n ? p : n - 1), p);
+        load_aux(first + (p < n ? p : n - 1), p);
+    }
+    to_lds(0, 0);
+    load(first + (PF < n ? PF : n - 1), 0);
+    __syncthreads();
+    int done = 0;
+    bool running = true;
+    while (running) {
+#pragma unroll
+        for (int p = 0; p < PF; ++p) {
+            const int i = first + done;
+            const int rb = p & 1, nslot = (p + 1) % PF;
+            const float* mine = &tiles[(rb * ROWS + rowl) * STRIDE + colw];
+            float* mu_out = mub + (size_t)i * TT;
+            const float d = read_shift<G>(sm, buf);
+            kappa += read_drift<G>(sm, buf);
+            O += (double)d;
+            float ua[4];
+#pragma unroll
+            for (int k = 0; k < 4; ++k) ua[k] = sm.rvec[buf][rowl + LPR * k] - d;  // -inf for rows >= T
+            const float K = feasible ? (float)(O + ob[p] - lz2) + kappa : LCCRF_NEG_INF;
+            float ubK[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) ubK[j] = (colw + j < T) ? aux[p][j] + K : LCCRF_NEG_INF;
+            {
+                const int ahead = done + PF;
+                load_aux(first + (ahead < n ? ahead : n - 1), p);
+            }
+            // tile i + 1 goes to the other LDS buffer; its ring slot takes tile i + 1 + PF
+            to_lds(nslot, nslot & 1);
+            {
+                const int ahead = done + 1 + PF;
+                load(first + (ahead < n ? ahead : n - 1), nslot);
+            }
+            const int flag = nstep & 3;
+            if (tid == 0) sm.bad[(nstep + 1) & 3] = 0;
+            if (!exact_only) {
+                float ls[4] = {0.f, 0.f, 0.f, 0.f}, gm[4];
+#pragma unroll
+                for (int j = 0; j < 4; ++j) gm[j] = ex2(d + ubK[j]);
+#pragma unroll
+                for (int k = 0; k < 4; ++k) {
+                    const float uac = ua[k] - d;  // shift c = d, the previous normaliser
+                    const float4 q = *reinterpret_cast<const float4*>(mine + LPR * k * STRIDE);
+                    const float e0 = ex2(__builtin_fmaf(q.x, kLog2e, uac)), e1 = ex2(__builtin_fmaf(q.y, kLog2e, uac));
+                    const float e2 = ex2(__builtin_fmaf(q.z, kLog2e, uac)), e3 = ex2(__builtin_fmaf(q.w, kLog2e, uac));
+                    ls[0] += e0; ls[1] += e1; ls[2] += e2; ls[3] += e3;
+                    store4<true, false>(mu_out, T, rowl + LPR * k, colw, e0 * gm[0], e1 * gm[1], e2 * gm[2], e3 * gm[3]);
+                }
+                float tot = (ls[0] * gm[0] + ls[1] * gm[1]) + (ls[2] * gm[2] + ls[3] * gm[3]);
+                tot = xor_sum<1, 64>(tot);
+                if (lane == 0) sm.wtot[buf ^ 1][wave] = tot;
+                const float S = reduce4_over_lanes<LPR>(ls[0], ls[1], ls[2], ls[3], lane);
+                const int col = colw + kk;
+                const float r = (col < T) ? d + lg2(S) : LCCRF_NEG_INF;
+                if (rowl < 4) sm.rvec[buf ^ 1][col] = r;
+                const float wm = xor_max<LPR, 64>(xor_max<1, 4>(r));
+                if (lane == 0) sm.wmax[buf ^ 1][wave] = wm;
+                const bool ok = col >= T || sum_in_range(S);
+                if (!__all(ok) && lane == 0) sm.bad[flag] = 1;
+                __syncthreads();
+            }
+            if (exact_only || sm.bad[flag] != 0) {
+                // exact step: every log-sum-exp against its own maximum, all inside the wave; the marginals again
+                float v[4][4];
+                float lm[4] = {LCCRF_NEG_INF, LCCRF_NEG_INF, LCCRF_NEG_INF, LCCRF_NEG_INF};
+#pragma unroll
+                for (int k = 0; k < 4; ++k) {
+                    const float4 q = *reinterpret_cast<const float4*>(mine + LPR * k * STRIDE);
+                    v[k][0] = __builtin_fmaf(q.x, kLog2e, ua[k]);
+                    v[k][1] = __builtin_fmaf(q.y, kLog2e, ua[k]);
+                    v[k][2] = __builtin_fmaf(q.z, kLog2e, ua[k]);
+                    v[k][3] = __builtin_fmaf(q.w, kLog2e, ua[k]);
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) lm[j] = fmaxf(lm[j], v[k][j]);
+                }
+                float r[4], g[4], gx[4], Sl[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    lm[j] = xor_max<1, LPR>(lm[j]);
+                    g[j] = finite_or_zero(lm[j]);
+                    gx[j] = ex2(g[j] + ubK[j]);
+                }
+#pragma unroll
+                for (int k = 0; k < 4; ++k) {
+                    float ex[4];
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        ex[j] = ex2(v[k][j] - g[j]);
+                        Sl[j] += ex[j];
+                    }
+                    store4<true, false>(mu_out, T, rowl + LPR * k, colw, ex[0] * gx[0], ex[1] * gx[1], ex[2] * gx[2], ex[3] * gx[3]);
+                }
+                float tot = (Sl[0] * gx[0] + Sl[1] * gx[1]) + (Sl[2] * gx[2] + Sl[3] * gx[3]);
+                tot = xor_sum<1, 64>(tot);
+#pragma unroll
+                for (int j = 0; j < 4; ++j) r[j] = (colw + j < T) ? lm[j] + lg2(xor_sum<1, LPR>(Sl[j])) : LCCRF_NEG_INF;
+                __syncthreads();  // nobody still reads the rejected vector
+                if (rowl == 0) *reinterpret_cast<float4*>(&sm.rvec[buf ^ 1][colw]) = make_float4(r[0], r[1], r[2], r[3]);
+                const float wm = xor_max<LPR, 64>(fmaxf(fmaxf(r[0], r[1]), fmaxf(r[2], r[3])));
+                if (lane == 0) {
+                    sm.wmax[buf ^ 1][wave] = wm;
+                    sm.wtot[buf ^ 1][wave] = tot;
+                }
+                __syncthreads();
+            }
+            buf ^= 1;
+            ++nstep;
+            if (++done >= n) { running = false; break; }
+        }
+    }
 }
 
 // ---------------------------------------------------------------------------------------
@@ -616,6 +785,13 @@ __global__ __launch_bounds__(G::W) void chain_marginal_kernel(ChainArgs a) {
     const bool feasible = lz2 > -1.0e300;  // false: no path has a finite score, marginals are 0
     if (dir == 0 && sp.c == 0 && tid == 0 && a.logZ) a.logZ[b] = (float)(lz2 * kLn2);
 
+    if constexpr (marginal_turns<G, ALIGNED>() && !STRUCT) {
+        if (dir == 0) {
+            extern __shared__ __attribute__((aligned(16))) float turn_tiles[];
+            forward_marginal_turned<G, TIN>(sm, turn_tiles, a, sp, tid, lz2, feasible);
+            return;
+        }
+    }
     float ring[PF][ITEMS][4];
     int buf = 0, nstep = 0;
     float kappa = 0.f;  // running correction that keeps each position's marginals summing to one
@@ -755,7 +931,7 @@ static hipError_t launch_geo(int op, ChainArgs a, hipStream_t st, hipEvent_t bet
     hipError_t e = hipSuccess;
     size_t turn_bytes = 0;
     if constexpr (half_turns<G, ALIGNED, PF1>()) {
-        turn_bytes = kTurnFloats * sizeof(float);
+        turn_bytes = turn_floats<G>() * sizeof(float);
         e = hipFuncSetAttribute(reinterpret_cast<const void*>(&chain_half_kernel<G, TIN, ALIGNED, PF1>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)turn_bytes);
         if (e != hipSuccess) return e;
@@ -780,7 +956,14 @@ static hipError_t launch_geo(int op, ChainArgs a, hipStream_t st, hipEvent_t bet
         if (e != hipSuccess) return e;
         a.only_failed = pair.failed;
     }
-    hipLaunchKernelGGL((chain_marginal_kernel<G, TIN, ALIGNED, PF2>), dim3(2 * a.B * a.C), dim3(G::W), 0, st, a);
+    size_t turn2_bytes = 0;
+    if constexpr (marginal_turns<G, ALIGNED>()) {
+        turn2_bytes = turn_floats<G>() * sizeof(float);
+        e = hipFuncSetAttribute(reinterpret_cast<const void*>(&chain_marginal_kernel<G, TIN, ALIGNED, PF2>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)turn2_bytes);
+        if (e != hipSuccess) return e;
+    }
+    hipLaunchKernelGGL((chain_marginal_kernel<G, TIN, ALIGNED, PF2>), dim3(2 * a.B * a.C), dim3(G::W), turn2_bytes, st, a);
     return hipGetLastError();
 }
 

@@ -276,7 +276,7 @@ def test_dirty_workspace_and_side_stream(crf, oracle_mod):
 # ---------------------------------------------------------------------------------------
 # the two step flavours of the sequential schedule
 
-@pytest.mark.parametrize("T,N", [(5, 8), (16, 40), (32, 64), (48, 33), (100, 9), (128, 12), (255, 4)])
+@pytest.mark.parametrize("T,N", [(5, 8), (16, 40), (32, 64), (36, 44), (48, 33), (64, 30), (100, 9), (128, 12), (255, 4)])
 def test_exact_schedule(crf, oracle_mod, T, N):
     """Every position through the exact step (the one that otherwise only replays rejected
     speculative steps)."""
@@ -285,7 +285,7 @@ def test_exact_schedule(crf, oracle_mod, T, N):
                queries=("logz", "mu"))
 
 
-@pytest.mark.parametrize("T,N", [(16, 64), (32, 40), (48, 21), (128, 10)])
+@pytest.mark.parametrize("T,N", [(16, 64), (32, 40), (36, 44), (48, 21), (60, 25), (64, 30), (128, 10)])
 def test_scale_jumps_force_replays(crf, oracle_mod, T, N):
     """Potentials whose scale jumps by hundreds of nats between neighbouring positions: the
     speculative step (shift = previous normaliser) must be rejected and replayed exactly, also
