@@ -242,7 +242,7 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="cfg4")
-    ap.add_argument("--algo", default="auto", choices=("auto", "sequential", "scan"),
+    ap.add_argument("--algo", default="auto", choices=("auto", "sequential", "scan", "lanes"),
                     help="schedule of the timed marginals call (profiles of a schedule AUTO would not take)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-other-queries", action="store_true")
@@ -313,7 +313,8 @@ def main():
         if args.cold:
             scratch.add_(1)
 
-    algo = {"auto": crf.ALGO_AUTO, "sequential": crf.ALGO_SEQUENTIAL, "scan": crf.ALGO_SCAN}[args.algo]
+    algo = {"auto": crf.ALGO_AUTO, "sequential": crf.ALGO_SEQUENTIAL, "scan": crf.ALGO_SCAN,
+            "lanes": crf.ALGO_SEQUENTIAL_LANES}[args.algo]
 
     def run_step(evs=None):
         evict()

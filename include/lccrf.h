@@ -87,9 +87,16 @@ typedef enum {
                                   on its own.  T <= 32 for the sum queries, T <= 16 for lccrf_argmax, else
                                   LCCRF_ENOTIMPL;
                                   AUTO takes it for long chains in small batches */
-    LCCRF_ALGO_SEQUENTIAL_EXACT = 3 /* sequential, and every log-sum-exp shifted by its own maximum:
+    LCCRF_ALGO_SEQUENTIAL_EXACT = 3, /* sequential, and every log-sum-exp shifted by its own maximum:
                                   the step that normally only replays rejected speculative steps
                                   is used for every position (same results up to rounding; slower) */
+    LCCRF_ALGO_SEQUENTIAL_LANES = 4  /* sequential, the recursion in scaled probabilities by one wave per
+                                  chain (a step is a vector-matrix product, one tag per lane) while the
+                                  other waves of its workgroup stream and exponentiate the potentials and
+                                  write the marginals; positions whose sums leave the range of single
+                                  precision (or hold -inf) are taken in the log domain.  lccrf_log_partition
+                                  and lccrf_marginals only, 8 <= T <= 64 with T a multiple of 4, else
+                                  LCCRF_ENOTIMPL; AUTO takes it where the batch leaves the chip latency-bound */
 } lccrf_algo;
 
 typedef enum {
@@ -313,7 +320,7 @@ int lccrf_set_scan_chunk(int chunk);
 int lccrf_set_pair_poll_limit(int polls);
 
 /* The schedule LCCRF_ALGO_AUTO takes for `op` at this shape under the current chunk size:
- * LCCRF_ALGO_SEQUENTIAL or LCCRF_ALGO_SCAN.  Host-side arithmetic, nothing is launched;
+ * LCCRF_ALGO_SEQUENTIAL, LCCRF_ALGO_SEQUENTIAL_LANES or LCCRF_ALGO_SCAN.  Host-side arithmetic, nothing is launched;
  * LCCRF_EINVAL for a shape or op the library does not serve.  For callers that size or time a run
  * by the schedule it will take (the benchmark names its dominant kernel from it). */
 int lccrf_auto_algo(lccrf_op op, int B, int N, int T);

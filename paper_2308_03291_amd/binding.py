@@ -24,7 +24,7 @@ LIB_PATH = os.path.join(_HERE, "liblccrf.so")
 
 LCCRF_F32, LCCRF_BF16 = 0, 1
 OP_LOGZ, OP_MARGINALS, OP_ARGMAX, OP_LOG_PROB, OP_ENTROPY, OP_SAMPLE, OP_CROSS_ENTROPY = 0, 1, 2, 3, 4, 5, 6
-ALGO_AUTO, ALGO_SEQUENTIAL, ALGO_SCAN, ALGO_SEQUENTIAL_EXACT = 0, 1, 2, 3
+ALGO_AUTO, ALGO_SEQUENTIAL, ALGO_SCAN, ALGO_SEQUENTIAL_EXACT, ALGO_SEQUENTIAL_LANES = 0, 1, 2, 3, 4
 MAX_T = 256
 
 EXPORTS = (
@@ -124,7 +124,7 @@ def set_pair_poll_limit(polls: int) -> None:
 
 
 def auto_algo(op: int, B: int, N: int, T: int) -> int:
-    """The schedule ALGO_AUTO takes for `op` at this shape: ALGO_SEQUENTIAL or ALGO_SCAN."""
+    """The schedule ALGO_AUTO takes for `op` at this shape: ALGO_SEQUENTIAL, ALGO_SEQUENTIAL_LANES or ALGO_SCAN."""
     rc = load_library().lccrf_auto_algo(int(op), int(B), int(N), int(T))
     if rc < 0:
         _check(rc, "lccrf_auto_algo")

@@ -177,7 +177,7 @@ lccrf::ScanGroupBuffers group_buffers(const SumWorkspace& w, char* base) {
 int check_common(const void* phi, int dt, int B, int N, int T, const void* ws, size_t ws_bytes, size_t need,
                  int algo) {
     if (!shape_ok(B, N, T) || !dtype_ok(dt)) return LCCRF_EINVAL;
-    if (algo < LCCRF_ALGO_AUTO || algo > LCCRF_ALGO_SEQUENTIAL_EXACT) return LCCRF_EINVAL;
+    if (algo < LCCRF_ALGO_AUTO || algo > LCCRF_ALGO_SEQUENTIAL_LANES) return LCCRF_EINVAL;
     if (!phi) return LCCRF_ENULL;
     if (!ws || ws_bytes < need) return LCCRF_EWORKSPACE;
     if (!aligned_to(phi, 16) || !aligned_to(ws, kAlign)) return LCCRF_EALIGN;
@@ -214,6 +214,26 @@ inline bool scan_pays_entropy(int B, int N, int T) {
 // Sampling under the scan runs every chunk's forward chain with the one-wave kernels (32 tags at most).
 inline bool scan_pays_sample(int B, int N, int T) { return T <= 32 && scan_pays_sum(B, N, T); }
 
+// Whether LCCRF_ALGO_AUTO takes the chain-wave / producer-wave kernels (lccrf_lane.hip) for a sum query
+// (op 0: log-partition, 1: marginals).  Their time is set by the serial depth alone, about 12 us plus 0.35 us
+// a position at 17 .. 32 tags (0.45 .. 0.6 us at 33 .. 48), as long as every half chain has a compute unit to
+// itself; the one-wave and four-wave kernels take 0.7 .. 0.9 us a position, the scan some 30 us plus 2.9 ns a
+// position of the whole batch at 17 .. 32 tags.  Measured (marginals, us; lanes / scan / sequential):
+// B=128 N=256 T=32 102 / 122 / 197, B=256 N=256 T=32 168 / 246 / 227, B=32 N=64 T=32 38 / 40 / 57,
+// B=32 N=256 T=32 98 / 61 / 193, B=128 N=128 T=48 92 / 216 / 133, B=64 N=64 T=48 47 / 78 / 73.  Up to 16 tags the
+// scan is cheaper wherever the batch is small enough for these kernels; above 48 tags the second pass does not
+// pay (its producers spill), the first still does (B=32 N=256 T=64 log-partition 76 / 121 / 108).
+inline bool lanes_pay_sum(int op, int B, int N, int T) {
+    if (!lccrf::lane_chains_supported(T) || T <= 16) return false;
+    const int cus = current_device_cus();
+    if (T <= 32) {
+        if (B > cus) return false;
+        return !scan_pays_sum(B, N, T) || (double)N * (0.35 - 0.0029 * B) < 18.0;
+    }
+    if (2 * B > cus || scan_pays_sum(B, N, T)) return false;
+    return T <= 48 || op == 0;
+}
+
 int sum_query(int op, const void* phi, int dt, const int32_t* lengths, int B, int N, int T, float* logZ,
               float* marginals, void* workspace, size_t workspace_bytes, void* stream, int algo,
               void* ev_begin = nullptr, void* ev_between = nullptr, void* ev_end = nullptr) {
@@ -226,11 +246,13 @@ int sum_query(int op, const void* phi, int dt, const int32_t* lengths, int B, in
     if ((logZ && !aligned_to(logZ, 4)) || (marginals && !aligned_to(marginals, 16))) return LCCRF_EALIGN;
     if (lengths && !aligned_to(lengths, 4)) return LCCRF_EALIGN;
     if (algo == LCCRF_ALGO_SCAN && !lccrf::scan_supported(T)) return LCCRF_ENOTIMPL;
+    if (algo == LCCRF_ALGO_SEQUENTIAL_LANES && !lccrf::lane_chains_supported(T)) return LCCRF_ENOTIMPL;
+    const bool lanes = algo == LCCRF_ALGO_SEQUENTIAL_LANES || (algo == LCCRF_ALGO_AUTO && lanes_pay_sum(op, B, N, T));
     const SumWorkspace w = sum_workspace(B, N, T);
     char* base = static_cast<char*>(workspace);
     hipStream_t st = static_cast<hipStream_t>(stream);
     if (ev_begin && hipEventRecord(static_cast<hipEvent_t>(ev_begin), st) != hipSuccess) return LCCRF_ELAUNCH;
-    if (algo == LCCRF_ALGO_SCAN || (algo == LCCRF_ALGO_AUTO && scan_pays_sum(B, N, T))) {
+    if (algo == LCCRF_ALGO_SCAN || (algo == LCCRF_ALGO_AUTO && !lanes && scan_pays_sum(B, N, T))) {
         float* Fv = reinterpret_cast<float*>(base + w.Fv);
         double* OF = reinterpret_cast<double*>(base + w.OF);
         float* Gv = reinterpret_cast<float*>(base + w.Gv);
@@ -256,7 +278,7 @@ int sum_query(int op, const void* phi, int dt, const int32_t* lengths, int B, in
         static_cast<hipEvent_t>(ev_between), algo == LCCRF_ALGO_SEQUENTIAL_EXACT,
         algo == LCCRF_ALGO_AUTO ? reinterpret_cast<unsigned long long*>(base + w.mail) : nullptr,
         reinterpret_cast<int*>(base + w.failed), nullptr, nullptr, nullptr,
-        g_pair_poll_limit.load(std::memory_order_relaxed), algo == LCCRF_ALGO_AUTO ? current_device_cus() : 0);
+        g_pair_poll_limit.load(std::memory_order_relaxed), algo == LCCRF_ALGO_AUTO ? current_device_cus() : 0, lanes);
     if (e != hipSuccess) return LCCRF_ELAUNCH;
     if (ev_end && hipEventRecord(static_cast<hipEvent_t>(ev_end), st) != hipSuccess) return LCCRF_ELAUNCH;
     return LCCRF_OK;
@@ -288,6 +310,9 @@ int lccrf_auto_algo(lccrf_op op, int B, int N, int T) {
     switch (op) {
         case LCCRF_OP_LOGZ:
         case LCCRF_OP_MARGINALS:
+            if (lanes_pay_sum(op == LCCRF_OP_LOGZ ? 0 : 1, B, N, T)) return LCCRF_ALGO_SEQUENTIAL_LANES;
+            scan = scan_pays_sum(B, N, T);
+            break;
         case LCCRF_OP_LOG_PROB: scan = scan_pays_sum(B, N, T); break;
         case LCCRF_OP_SAMPLE: scan = scan_pays_sample(B, N, T); break;
         case LCCRF_OP_ARGMAX: scan = scan_pays_max(B, N, T); break;
@@ -329,6 +354,7 @@ int lccrf_argmax_algo(const void* phi, lccrf_dtype dt, const int32_t* lengths, i
     if (!aligned_to(tags, 4) || (best_score && !aligned_to(best_score, 4))) return LCCRF_EALIGN;
     if (lengths && !aligned_to(lengths, 4)) return LCCRF_EALIGN;
     if (algo == LCCRF_ALGO_SCAN && !lccrf::scan_supported_max(T)) return LCCRF_ENOTIMPL;
+    if (algo == LCCRF_ALGO_SEQUENTIAL_LANES) return LCCRF_ENOTIMPL;  // (a sum-product schedule)
     const MaxWorkspace w = max_workspace(B, N, T);
     char* base = static_cast<char*>(workspace);
     hipStream_t st = static_cast<hipStream_t>(stream);

@@ -1031,6 +1031,7 @@ static hipError_t launch_stream(int op, int dtype, const ChainArgs& a, hipStream
 }
 
 bool structured_supported(int T) { return T >= 1 && T <= 128; }
+bool lane_chains_supported(int T) { return lane_supported(T); }
 
 // Forward chains over whole sequences, every alpha stored (ua, Oa): the first pass of sampling.
 hipError_t launch_full_forward(int dtype, const void* phi, const int32_t* lengths, int B, int N, int T, float* ua,
@@ -1061,12 +1062,26 @@ hipError_t launch_sequential_sum(int op, int dtype, const void* phi, const int32
                                  float* ua, float* ub, double* Oa, double* Ob, float* logZ, float* mu,
                                  hipStream_t st, hipEvent_t between, bool exact_only, unsigned long long* mail,
                                  int* failed, double* logZ64, const float* emit, const float* trans, int pair_poll_limit,
-                                 int cus) {
+                                 int cus, bool lanes) {
     ChainArgs a{phi, lengths, B, N, T, ua, ub, Oa, Ob, logZ, mu, exact_only ? 1 : 0, nullptr, 0, 1, nullptr, nullptr, nullptr, nullptr};
     a.logZ64 = logZ64;
     a.emit = emit;
     a.trans = trans;
     if (emit && T > 128) return hipErrorInvalidValue;  // the caller checks structured_supported(T) first
+    if (lanes) {
+        if (emit || exact_only || !lane_supported(T)) return hipErrorInvalidValue;
+        hipError_t e = launch_lane_pass(false, dtype, a, op == 0, st);
+        if (e != hipSuccess) return e;
+        if (between) {
+            e = hipEventRecord(between, st);
+            if (e != hipSuccess) return e;
+        }
+        if (op == 0) {
+            hipLaunchKernelGGL(logz_combine_kernel, dim3(a.B), dim3(64), 0, st, a);
+            return hipGetLastError();
+        }
+        return launch_lane_pass(true, dtype, a, false, st);
+    }
     if (wave_supported(T) && op == 1 && !emit && wave_chunks_fused(N - 1)) {
         // Short sequences: both passes in one launch, the vectors in LDS (as for the chunks of the scan).
         if (between) {

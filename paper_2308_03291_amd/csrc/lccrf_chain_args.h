@@ -109,5 +109,10 @@ hipError_t launch_stream_pass(bool second_pass, int dtype, const ChainArgs& a, h
 // 2: KL divergence, with a.psi and a.hoff), leaving what entropy_half_kernel leaves (lccrf_extras.hip).
 hipError_t launch_stream_expect(int mode, int dtype, const ChainArgs& a, hipStream_t st);
 hipError_t launch_wave_chunks(int dtype, const ChainArgs& a, hipStream_t st);
+// One chain wave and six producer waves per half chain (lccrf_lane.hip): plain potentials, whole
+// sequences, 8 <= T <= 64 in multiples of four.  One pass over all sequences of `a`, vectors and marginals
+// exactly as launch_wave_pass; meet_only: a first pass that stores the vectors of the meeting position only.
+bool lane_supported(int T);
+hipError_t launch_lane_pass(bool second_pass, int dtype, const ChainArgs& a, bool meet_only, hipStream_t st);
 
 }  // namespace lccrf

@@ -21,7 +21,9 @@ hipError_t launch_sequential_sum(int op, int dtype, const void* phi, const int32
                                  hipStream_t st, hipEvent_t between = nullptr, bool exact_only = false,
                                  unsigned long long* mail = nullptr, int* failed = nullptr, double* logZ64 = nullptr,
                                  const float* emit = nullptr, const float* trans = nullptr, int pair_poll_limit = 0,
-                                 int cus = 0);
+                                 int cus = 0, bool lanes = false);
+// lanes: the chain-wave / producer-wave kernels of lccrf_lane.hip (lane_chains_supported(T), plain potentials).
+bool lane_chains_supported(int T);
 // Sampling (lccrf_chain.hip, lccrf_extras.hip): forward chains over whole sequences with every alpha
 // stored, then the backward sweep that draws the tags from the given uniforms [B][N].
 hipError_t launch_full_forward(int dtype, const void* phi, const int32_t* lengths, int B, int N, int T, float* ua,
