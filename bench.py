@@ -190,9 +190,11 @@ def bench_config(crf, workloads, oracle, torch, timer, key, calls, dev, with_par
            "effective_potentials": eff_pots, "working_set_bytes": working_set, "queries": {}}
     scan_any = False
     for name, (fn, bpp, op) in queries.items():
-        scan = crf.auto_algo(op, w.B, w.N, w.T) == crf.ALGO_SCAN
+        taken = crf.auto_algo(op, w.B, w.N, w.T)
+        scan = taken == crf.ALGO_SCAN
         scan_any = scan_any or (scan and name == "marginals")
-        q = {"schedule": "scan" if scan else "sequential", "algorithmic_bytes": eff_pots * bpp,
+        q = {"schedule": "scan" if scan else "sequential (chain wave + producer waves)" if taken == crf.ALGO_SEQUENTIAL_LANES
+             else "sequential", "algorithmic_bytes": eff_pots * bpp,
              "warm": timer.run(fn, calls, cold=False)}
         states = ["warm"]
         if working_set < CACHE_BYTES:
@@ -346,8 +348,13 @@ def main():
 
     value = pots / (ms_per_step * 1e-3)
     call_bytes = eff_pots * (2 * esz + 4)
-    scan_taken = algo == crf.ALGO_SCAN or (algo == crf.ALGO_AUTO and crf.auto_algo(crf.OP_MARGINALS, w.B, w.N, w.T) == crf.ALGO_SCAN)
-    if w.T <= 32 and (scan_taken or 2 <= w.N <= 65):
+    auto_taken = crf.auto_algo(crf.OP_MARGINALS, w.B, w.N, w.T)
+    scan_taken = algo == crf.ALGO_SCAN or (algo == crf.ALGO_AUTO and auto_taken == crf.ALGO_SCAN)
+    lanes_taken = algo == crf.ALGO_SEQUENTIAL_LANES or (algo == crf.ALGO_AUTO and auto_taken == crf.ALGO_SEQUENTIAL_LANES)
+    if lanes_taken:
+        # second pass of the chain-wave / producer-wave kernels: one read of phi + one write of mu
+        kernel, alg_bytes = "lane_chain_kernel (second pass)", eff_pots * (esz + 4)
+    elif w.T <= 32 and (scan_taken or 2 <= w.N <= 65):
         # Chunked scan: the interval after the boundary phases is one kernel that makes both passes over
         # every chunk (two reads of phi, the second from cache at best, and one write of mu).  Sequences of
         # at most 65 positions over at most 32 tags take the same kernel whole.
@@ -370,7 +377,8 @@ def main():
                 # counters cannot be read inside the run: this figure comes from the committed rocprofv3 --pmc summary
                 "traffic": committed_traffic(w.key), "traffic_source": f"profiles/marginals_{w.key}_traffic.txt (committed)",
                 "algorithmic_bytes_per_launch": alg_bytes, "avg_launch_ms": pass2_avg,
-                "first_pass": {"kernel": "chain_half_kernel", "algorithmic_bytes": eff_pots * esz,
+                "first_pass": {"kernel": "lane_chain_kernel (first pass)" if lanes_taken else "chain_half_kernel",
+                               "algorithmic_bytes": eff_pots * esz,
                                "avg_ms": sum(pass1) / len(pass1),
                                "frac": eff_pots * esz / (sum(pass1) / len(pass1) * 1e-3) / 1e9 / HBM_PEAK_GBPS},
                 "whole_call": {"algorithmic_bytes": call_bytes, "avg_ms": sum(whole) / len(whole),

@@ -34,8 +34,11 @@
 
 namespace lccrf {
 
-constexpr int kLaneWaves = 8;           // wave 0: the chain (at raised priority); waves 1 .. 7: producers
-constexpr int kLaneProducers = 7;
+// Waves of a workgroup: wave 0 runs the chain (at raised priority), the others are producers.  Up to 32 tags a
+// producer needs few registers and eleven of them keep the second pass fed (B=128 N=256 T=32: second pass
+// 51.8 -> 47.9 us against seven); above, seven is what the register file holds at two waves a SIMD.
+constexpr int lane_waves(int nblk) { return nblk <= 2 ? 12 : 8; }
+constexpr int kLaneMaxProducers = 11;
 constexpr int kLaneVecRing = 16;        // published vectors kept (the chain leads a producer by fewer than that)
 constexpr int kLanePollLimit = 1 << 16; // polls of an LDS flag before a wave stops waiting
 
@@ -57,7 +60,7 @@ struct LaneShared {
     float V[kLaneVecRing][64];      // V_q, the vector that enters step q, at [q % kLaneVecRing]
     int VOi[kLaneVecRing];          // its offset less O0 (the shifts and rescales so far: an integer)
     double O0;                      // offset of V_0
-    float G[kLaneProducers][64];    // per producer wave: the factors of the stored vector of the other chain
+    float G[kLaneMaxProducers][64]; // per producer wave: the factors of the stored vector of the other chain
     unsigned long long ready[S::RING];  // once the matrix of step q sits in slot q % RING: q + 1 in the high word,
                                         // the matrix's shift (an integer) in the low word: one read brings both
     int done;                       // steps the chain has accepted
@@ -221,9 +224,6 @@ __device__ __forceinline__ void lane_chain_wave(const ChainArgs& a, const LaneJo
     unsigned q = 0;
     const unsigned count = (unsigned)jb.count;
     bool tail = false;
-#ifdef LCCRF_LANE_PROFILE
-    const long long prof_t0 = clock64();
-#endif
     // The matrix of a step: the entries of this lane in the order its rotations consume them, and the shift.
     constexpr int NB = kSplit ? 1 : NBLK;  // blocks of sixteen source tags a lane sums over
     struct Tile {
@@ -242,20 +242,11 @@ __device__ __forceinline__ void lane_chain_wave(const ChainArgs& a, const LaneJo
             }
     };
     // waits for the matrix of `step` (bounded) and reads it; false: it did not come
-#ifdef LCCRF_LANE_PROFILE
-    long long prof_miss = 0, prof_polls = 0;
-#endif
     const auto fetch = [&](unsigned step, Tile& t) -> bool {
         int spins = 0;
-#ifdef LCCRF_LANE_PROFILE
-        ++prof_miss;
-#endif
         unsigned long long word;
         while ((unsigned)__builtin_amdgcn_readfirstlane((int)((word = lds_load_acquire(&sh.ready[step % S::RING])) >> 32)) < step + 1)
             if (++spins > kLanePollLimit) return false;
-#ifdef LCCRF_LANE_PROFILE
-        prof_polls += spins;
-#endif
         read_tile(step, t, word);
         return true;
     };
@@ -263,8 +254,10 @@ __device__ __forceinline__ void lane_chain_wave(const ChainArgs& a, const LaneJo
     // already there (one look at its flag, early enough that the answer is back when the products are done),
     // else waited for at the end.  Everything the step leaves behind for the other waves is the vector, one
     // integer and the step count in LDS: the stores to memory are theirs.
-    // 0: done, 1: the step was not accepted, 2: the next matrix did not come.
-    const auto step = [&](const Tile& cur, Tile& nxt) -> int {
+    // 0: go on, 1: the step was not accepted, 2: the next matrix did not come, 3: that was the last step.
+    // (Flags and offsets are written by every lane, the same value to the same address: cheaper for a lone
+    // wave than masking the write down to one lane.)
+    const auto step = [&](const Tile& cur, Tile& nxt) __attribute__((always_inline)) -> int {
         unsigned long long word_next = lds_load_acquire(&sh.ready[(q + 1) % S::RING]);
         float Ab[4];
         if constexpr (NBLK == 1) {
@@ -301,32 +294,25 @@ __device__ __forceinline__ void lane_chain_wave(const ChainArgs& a, const LaneJo
         V = __builtin_amdgcn_ldexpf(Ssum, -k);
         Oi = Onew + k;
         ++q;
-        if (copy == 0) sh.V[q % kLaneVecRing][u] = V;
-        if (lane == 0) {
-            sh.VOi[q % kLaneVecRing] = Oi;
-            lds_store_release(&sh.done, (int)q);
-        }
-        if (q == count) return 0;
+        sh.V[q % kLaneVecRing][u] = V;
+        sh.VOi[q % kLaneVecRing] = Oi;
+        lds_store_release(&sh.done, (int)q);
+        if (q == count) return 3;
         if ((unsigned)__builtin_amdgcn_readfirstlane((int)(word_next >> 32)) >= q + 1) read_tile(q, nxt, word_next);
         else if (!fetch(q, nxt)) return 2;
         return 0;
     };
     Tile tA, tB;
-    if (count > 0 && !fetch(0, tA)) tail = true;
-    while (!tail && q < count) {
-        if (step(tA, tB) != 0) { tail = true; break; }
-        if (q >= count) break;
-        if (step(tB, tA) != 0) { tail = true; break; }
+    if (count > 0) {
+        int why = fetch(0, tA) ? 0 : 2;
+        while (why == 0) {
+            why = step(tA, tB);
+            if (why != 0) break;
+            why = step(tB, tA);
+        }
+        tail = why != 3;
     }
     O = O0 + (double)Oi;
-#ifdef LCCRF_LANE_PROFILE
-    if (lane == 0 && a.hoff) {
-        long long* pr = reinterpret_cast<long long*>(a.hoff) + (size_t)blockIdx.x * 8;
-        pr[0] += clock64() - prof_t0;
-        pr[1] += prof_miss * 1000000 + prof_polls;
-        pr[2] += q;
-    }
-#endif
     on = lane < T;  // from here on lane = tag again (the first copy)
     lv = on ? lg2(V) : LCCRF_NEG_INF;
     if (tail) {
@@ -349,7 +335,7 @@ template <int NBLK, typename TIN, bool PASS2>
 __device__ __forceinline__ void lane_producer_wave(const ChainArgs& a, const LaneJob& jb, LaneShared<NBLK>& sh, int w,
                                                    double lz2, int meet_only) {
     using S = LaneShape<NBLK>;
-    constexpr int NG = S::NG, PF = S::PF, W = kLaneProducers;
+    constexpr int NG = S::NG, PF = S::PF, W = lane_waves(NBLK) - 1;
     const int lane = threadIdx.x & 63, T = a.T, N = a.N, b = jb.b;
     const size_t TT = (size_t)T * T;
     const size_t vb = (size_t)b * N;
@@ -400,19 +386,6 @@ __device__ __forceinline__ void lane_producer_wave(const ChainArgs& a, const Lan
         }
         return true;
     };
-#ifdef LCCRF_LANE_PROFILE
-    long long prof_w1 = 0, prof_w2 = 0, prof_ld = 0, prof_ex = 0;
-    const long long prof_t0 = clock64();
-    const auto prof_flush = [&]() {
-        if (lane == 0 && w == 0 && a.hoff) {
-            long long* pr = reinterpret_cast<long long*>(a.hoff) + (size_t)blockIdx.x * 8;
-            pr[3] += clock64() - prof_t0; pr[4] += prof_w1; pr[5] += prof_w2; pr[6] += prof_ld; pr[7] += prof_ex;
-        }
-    };
-#define LCCRF_PROF(x) x
-#else
-#define LCCRF_PROF(x)
-#endif
     // One matrix (number j of this wave, in buffer p): exponentiate, hand to the chain, write its marginals.
     // false: the chain has stopped before this matrix, nothing more to do.
     const auto process = [&](int j, auto pc) -> bool {
@@ -421,7 +394,6 @@ __device__ __forceinline__ void lane_producer_wave(const ChainArgs& a, const Lan
         const int i = jb.first + q * jb.sdir;
         const int slot = q % S::RING;
         // the shift of this matrix: the smallest integer at or above its largest entry (base 2)
-        LCCRF_PROF(const long long pl0 = clock64(); asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); const long long pl1 = clock64(); prof_ld += pl1 - pl0;)
         float mxr = LCCRF_NEG_INF;
 #pragma unroll
         for (int m = 0; m < NG; ++m) {
@@ -435,9 +407,7 @@ __device__ __forceinline__ void lane_producer_wave(const ChainArgs& a, const Lan
 #pragma unroll
             for (int k = 0; k < 4; ++k) x[p][m][k] = ex2(__builtin_fmaf(x[p][m][k], kLog2e, -sh_m));
         // the slot is free once the chain has accepted step q - RING
-        LCCRF_PROF(const long long pw0 = clock64(); prof_ex += pw0 - pl1;)
         if (!wait_for(&sh.done, q - S::RING + 1, q)) return false;
-        LCCRF_PROF(prof_w1 += clock64() - pw0;)
         float* Es = &sh.E[slot][0][0];
 #pragma unroll
         for (int m = 0; m < NG; ++m)
@@ -449,9 +419,7 @@ __device__ __forceinline__ void lane_producer_wave(const ChainArgs& a, const Lan
             lds_store_release(&sh.ready[slot], ((unsigned long long)(unsigned)(q + 1) << 32) | (unsigned)(int)sh_m);
         if (PASS2) {
             // the chain has accepted step q: V_q and this matrix make the marginals of position i
-            LCCRF_PROF(const long long pw1 = clock64();)
             if (!wait_for(&sh.done, q + 1, q)) return false;
-            LCCRF_PROF(prof_w2 += clock64() - pw1;)
             const double Oq = sh.O0 + (double)sh.VOi[q % kLaneVecRing];
             const float c = (float)(Oq + (double)sh_m + oo[p] - lz2);
             sh.G[w][lane] = lane < T ? ex2(aux[p] + c) : 0.f;
@@ -492,13 +460,12 @@ __device__ __forceinline__ void lane_producer_wave(const ChainArgs& a, const Lan
         __builtin_amdgcn_sched_barrier(0);
         if (j + 1 < nj && !process(j + 1, Buf1{})) break;
     }
-    LCCRF_PROF(prof_flush();)
 }
-#undef LCCRF_PROF
 
 template <int NBLK, typename TIN, bool PASS2>
-__global__ __launch_bounds__(64 * kLaneWaves) void lane_chain_kernel(ChainArgs a, int meet_only) {
+__global__ __launch_bounds__(64 * lane_waves(NBLK)) void lane_chain_kernel(ChainArgs a, int meet_only) {
     using S = LaneShape<NBLK>;
+    constexpr int kLaneWaves = lane_waves(NBLK);
     extern __shared__ __attribute__((aligned(16))) unsigned char lane_smem[];
     LaneShared<NBLK>& sh = *reinterpret_cast<LaneShared<NBLK>*>(lane_smem);
     const int tid = threadIdx.x, lane = tid & 63;
@@ -587,7 +554,7 @@ static hipError_t launch_lane_kernel(const ChainArgs& a, int meet_only, hipStrea
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&lane_chain_kernel<NBLK, TIN, PASS2>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL((lane_chain_kernel<NBLK, TIN, PASS2>), dim3(2 * a.B), dim3(64 * kLaneWaves), bytes, st, a, meet_only);
+    hipLaunchKernelGGL((lane_chain_kernel<NBLK, TIN, PASS2>), dim3(2 * a.B), dim3(64 * lane_waves(NBLK)), bytes, st, a, meet_only);
     return hipGetLastError();
 }
 template <int NBLK>
