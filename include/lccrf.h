@@ -37,8 +37,9 @@
  *    them, and the launches before it are already enqueued: the outputs and the
  *    workspace are then unspecified, nothing else is harmed.
  *  - Thread safety: concurrent calls with distinct workspaces are safe.  The only
- *    mutable state in the library are two process-wide tuning knobs
- *    (lccrf_set_scan_chunk, lccrf_set_pair_poll_limit; atomic integers, meant to be
+ *    mutable state in the library are three process-wide tuning knobs
+ *    (lccrf_set_scan_chunk, lccrf_set_pair_poll_limit, lccrf_set_lane_poll_limit; atomic
+ *    integers, meant to be
  *    set once at start-up) and caches of per-device constants.  A call reads the
  *    knobs once, at its start, so every call is consistent in itself; a workspace
  *    sized under one chunk setting and used under another is refused with
@@ -49,7 +50,10 @@
  *    lccrf_set_pair_poll_limit); a pair that gives its sequence up hands it to the
  *    one-workgroup kernel, which rounds differently, so where that hand-over depends
  *    on timing two runs may differ in the low-order bits (far inside the tolerance).
- *    LCCRF_ALGO_SEQUENTIAL never uses pairs.
+ *    LCCRF_ALGO_SEQUENTIAL never uses pairs.  Likewise a chain of LCCRF_ALGO_SEQUENTIAL_LANES (which AUTO
+ *    takes for mid-sized batches of 17 .. 64 tags) whose producers fall behind its poll limit
+ *    (lccrf_set_lane_poll_limit; milliseconds, not seen in practice) finishes in the log domain and
+ *    rounds differently from a run in which they kept up.
  */
 #ifndef LCCRF_H
 #define LCCRF_H
@@ -318,6 +322,15 @@ int lccrf_set_scan_chunk(int chunk);
  * restores it, 0 gives up without looking (every sequence then takes the one-workgroup kernel: for
  * tests of that path), more than 2^24 returns LCCRF_EINVAL. */
 int lccrf_set_pair_poll_limit(int polls);
+
+/* How many times the chain wave of LCCRF_ALGO_SEQUENTIAL_LANES looks for a matrix that its producer waves have
+ * not delivered yet (one read of a word in LDS per look) before it stops waiting and finishes its half chain
+ * alone in the log domain, straight from memory (the same path that serves -inf potentials), so results never
+ * depend on the limit beyond rounding.  A process-wide tuning knob.  Default 65536 looks (a few milliseconds at
+ * worst; a matrix is normally there before it is asked for), -1 restores it, 0 gives up at the first look that
+ * fails (nearly every chain then runs in the log domain from its first position: for tests of that path), more
+ * than 2^24 returns LCCRF_EINVAL. */
+int lccrf_set_lane_poll_limit(int polls);
 
 /* The schedule LCCRF_ALGO_AUTO takes for `op` at this shape under the current chunk size:
  * LCCRF_ALGO_SEQUENTIAL, LCCRF_ALGO_SEQUENTIAL_LANES or LCCRF_ALGO_SCAN.  Host-side arithmetic, nothing is launched;

@@ -34,7 +34,7 @@ EXPORTS = (
     "lccrf_sample", "lccrf_semi_markov_log_partition", "lccrf_log_partition_structured",
     "lccrf_marginals_structured", "lccrf_argmax_structured", "lccrf_set_scan_chunk", "lccrf_auto_algo",
     "lccrf_strerror", "lccrf_version", "lccrf_marginals_static", "lccrf_static_scratch_bytes",
-    "lccrf_set_pair_poll_limit", "lccrf_stream_probe", "lccrf_stream_probe_bytes", "lccrf_sample_seeded",
+    "lccrf_set_pair_poll_limit", "lccrf_set_lane_poll_limit", "lccrf_stream_probe", "lccrf_stream_probe_bytes", "lccrf_sample_seeded",
 )
 
 _lib = None
@@ -102,6 +102,8 @@ def load_library() -> ctypes.CDLL:
     lib.lccrf_stream_probe_bytes.restype = sz
     lib.lccrf_set_pair_poll_limit.argtypes = [i]
     lib.lccrf_set_pair_poll_limit.restype = i
+    lib.lccrf_set_lane_poll_limit.argtypes = [i]
+    lib.lccrf_set_lane_poll_limit.restype = i
     lib.lccrf_auto_algo.argtypes = [i, i, i, i]
     lib.lccrf_auto_algo.restype = i
     _lib = lib
@@ -115,6 +117,11 @@ def strerror(code: int) -> str:
 def set_scan_chunk(chunk: int) -> None:
     """Positions per chunk of ALGO_SCAN (0: default).  Size workspaces after calling this."""
     _check(load_library().lccrf_set_scan_chunk(int(chunk)), "lccrf_set_scan_chunk")
+
+
+def set_lane_poll_limit(polls: int) -> None:
+    """Looks the chain wave of ALGO_SEQUENTIAL_LANES spends on a late matrix (-1: default, 0: none)."""
+    _check(load_library().lccrf_set_lane_poll_limit(int(polls)), "lccrf_set_lane_poll_limit")
 
 
 def set_pair_poll_limit(polls: int) -> None:

@@ -54,6 +54,10 @@ inline size_t round_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 // of milliseconds, four orders of magnitude above an exchange between resident partners (under 1 us).
 constexpr int kDefaultPairPollLimit = 1 << 15;
 std::atomic<int> g_pair_poll_limit{kDefaultPairPollLimit};
+// Polls the chain wave of the lane kernels spends on a matrix its producers have not delivered yet
+// (lccrf_set_lane_poll_limit) before it continues alone in the log domain.  A poll is one LDS read.
+constexpr int kDefaultLanePollLimit = 1 << 16;
+std::atomic<int> g_lane_poll_limit{kDefaultLanePollLimit};
 // Positions per chunk of the scan (lccrf_set_scan_chunk).  0: chosen by shape, the smallest of 8, 16 and 32 that keeps the
 // chunks of the batch (one wave each in the scan's first phase) within what the chip holds at once
 // (measured: short chunks win, 8 by 2.8 times on the marginals of B=1, N=128, T=32 against the
@@ -278,7 +282,8 @@ int sum_query(int op, const void* phi, int dt, const int32_t* lengths, int B, in
         static_cast<hipEvent_t>(ev_between), algo == LCCRF_ALGO_SEQUENTIAL_EXACT,
         algo == LCCRF_ALGO_AUTO ? reinterpret_cast<unsigned long long*>(base + w.mail) : nullptr,
         reinterpret_cast<int*>(base + w.failed), nullptr, nullptr, nullptr,
-        g_pair_poll_limit.load(std::memory_order_relaxed), algo == LCCRF_ALGO_AUTO ? current_device_cus() : 0, lanes);
+        g_pair_poll_limit.load(std::memory_order_relaxed), algo == LCCRF_ALGO_AUTO ? current_device_cus() : 0, lanes,
+        g_lane_poll_limit.load(std::memory_order_relaxed));
     if (e != hipSuccess) return LCCRF_ELAUNCH;
     if (ev_end && hipEventRecord(static_cast<hipEvent_t>(ev_end), st) != hipSuccess) return LCCRF_ELAUNCH;
     return LCCRF_OK;
@@ -721,6 +726,12 @@ int lccrf_set_pair_poll_limit(int polls) {
     return LCCRF_OK;
 }
 
-int lccrf_version(void) { return 200; }
+int lccrf_set_lane_poll_limit(int polls) {
+    if (polls < -1 || polls > (1 << 24)) return LCCRF_EINVAL;
+    g_lane_poll_limit.store(polls < 0 ? kDefaultLanePollLimit : polls, std::memory_order_relaxed);
+    return LCCRF_OK;
+}
+
+int lccrf_version(void) { return 201; }
 
 }  // extern "C"

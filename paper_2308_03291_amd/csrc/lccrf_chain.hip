@@ -1062,7 +1062,7 @@ hipError_t launch_sequential_sum(int op, int dtype, const void* phi, const int32
                                  float* ua, float* ub, double* Oa, double* Ob, float* logZ, float* mu,
                                  hipStream_t st, hipEvent_t between, bool exact_only, unsigned long long* mail,
                                  int* failed, double* logZ64, const float* emit, const float* trans, int pair_poll_limit,
-                                 int cus, bool lanes) {
+                                 int cus, bool lanes, int lane_poll_limit) {
     ChainArgs a{phi, lengths, B, N, T, ua, ub, Oa, Ob, logZ, mu, exact_only ? 1 : 0, nullptr, 0, 1, nullptr, nullptr, nullptr, nullptr};
     a.logZ64 = logZ64;
     a.emit = emit;
@@ -1070,7 +1070,7 @@ hipError_t launch_sequential_sum(int op, int dtype, const void* phi, const int32
     if (emit && T > 128) return hipErrorInvalidValue;  // the caller checks structured_supported(T) first
     if (lanes) {
         if (emit || exact_only || !lane_supported(T)) return hipErrorInvalidValue;
-        hipError_t e = launch_lane_pass(false, dtype, a, op == 0, st);
+        hipError_t e = launch_lane_pass(false, dtype, a, op == 0, lane_poll_limit, st);
         if (e != hipSuccess) return e;
         if (between) {
             e = hipEventRecord(between, st);
@@ -1080,7 +1080,7 @@ hipError_t launch_sequential_sum(int op, int dtype, const void* phi, const int32
             hipLaunchKernelGGL(logz_combine_kernel, dim3(a.B), dim3(64), 0, st, a);
             return hipGetLastError();
         }
-        return launch_lane_pass(true, dtype, a, false, st);
+        return launch_lane_pass(true, dtype, a, false, lane_poll_limit, st);
     }
     if (wave_supported(T) && op == 1 && !emit && wave_chunks_fused(N - 1)) {
         // Short sequences: both passes in one launch, the vectors in LDS (as for the chunks of the scan).

@@ -111,8 +111,9 @@ hipError_t launch_stream_expect(int mode, int dtype, const ChainArgs& a, hipStre
 hipError_t launch_wave_chunks(int dtype, const ChainArgs& a, hipStream_t st);
 // One chain wave and six producer waves per half chain (lccrf_lane.hip): plain potentials, whole
 // sequences, 8 <= T <= 64 in multiples of four.  One pass over all sequences of `a`, vectors and marginals
-// exactly as launch_wave_pass; meet_only: a first pass that stores the vectors of the meeting position only.
+// exactly as launch_wave_pass; meet_only: a first pass that stores the vectors of the meeting position only;
+// poll_limit: how many times the chain wave looks for a matrix that is late before it goes on alone.
 bool lane_supported(int T);
-hipError_t launch_lane_pass(bool second_pass, int dtype, const ChainArgs& a, bool meet_only, hipStream_t st);
+hipError_t launch_lane_pass(bool second_pass, int dtype, const ChainArgs& a, bool meet_only, int poll_limit, hipStream_t st);
 
 }  // namespace lccrf

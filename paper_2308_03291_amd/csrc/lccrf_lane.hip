@@ -40,7 +40,6 @@ namespace lccrf {
 constexpr int lane_waves(int nblk) { return nblk <= 2 ? 12 : 8; }
 constexpr int kLaneMaxProducers = 11;
 constexpr int kLaneVecRing = 16;        // published vectors kept (the chain leads a producer by fewer than that)
-constexpr int kLanePollLimit = 1 << 16; // polls of an LDS flag before a wave stops waiting
 
 template <int NBLK>
 struct LaneShape {
@@ -177,7 +176,7 @@ __device__ __forceinline__ void lane_log_tail(const ChainArgs& a, const LaneJob&
 // The chain wave.
 template <int NBLK, typename TIN, bool PASS2>
 __device__ __forceinline__ void lane_chain_wave(const ChainArgs& a, const LaneJob& jb, LaneShared<NBLK>& sh, double lz2,
-                                                bool feasible, int meet_only) {
+                                                bool feasible, int meet_only, int poll_limit) {
     using S = LaneShape<NBLK>;
     const int lane = threadIdx.x & 63, T = a.T, N = a.N, b = jb.b;
     const size_t TT = (size_t)T * T;
@@ -246,7 +245,7 @@ __device__ __forceinline__ void lane_chain_wave(const ChainArgs& a, const LaneJo
         int spins = 0;
         unsigned long long word;
         while ((unsigned)__builtin_amdgcn_readfirstlane((int)((word = lds_load_acquire(&sh.ready[step % S::RING])) >> 32)) < step + 1)
-            if (++spins > kLanePollLimit) return false;
+            if (++spins > poll_limit) return false;
         read_tile(step, t, word);
         return true;
     };
@@ -333,7 +332,7 @@ __device__ __forceinline__ void lane_chain_wave(const ChainArgs& a, const LaneJo
 // A producer wave.
 template <int NBLK, typename TIN, bool PASS2>
 __device__ __forceinline__ void lane_producer_wave(const ChainArgs& a, const LaneJob& jb, LaneShared<NBLK>& sh, int w,
-                                                   double lz2, int meet_only) {
+                                                   double lz2, int meet_only, int poll_limit) {
     using S = LaneShape<NBLK>;
     constexpr int NG = S::NG, PF = S::PF, W = lane_waves(NBLK) - 1;
     const int lane = threadIdx.x & 63, T = a.T, N = a.N, b = jb.b;
@@ -376,12 +375,12 @@ __device__ __forceinline__ void lane_producer_wave(const ChainArgs& a, const Lan
         }
     };
     // Waits until the flag reaches `target` (true) or the chain has stopped at or before step `q` (false).
-    // The chain wave always does one or the other: each of its own waits is bounded by kLanePollLimit.
-    // The limit here, a thousand times that, is a last resort that only keeps a wave from spinning for ever.
+    // The chain wave always does one or the other: each of its own waits is bounded by the poll limit of the call.
+    // The limit here, a thousand times the default, is a last resort that only keeps a wave from spinning for ever.
     const auto wait_for = [&](const int* flag, int target, int q) -> bool {
         long long spins = 0;
         while (lds_load_acquire(flag) < target) {
-            if (lds_load_acquire(&sh.stop) <= q || ++spins > 1000ll * kLanePollLimit) return false;
+            if (lds_load_acquire(&sh.stop) <= q || ++spins > 1000ll * (poll_limit + 65536)) return false;
             __builtin_amdgcn_s_sleep(1);
         }
         return true;
@@ -463,7 +462,7 @@ __device__ __forceinline__ void lane_producer_wave(const ChainArgs& a, const Lan
 }
 
 template <int NBLK, typename TIN, bool PASS2>
-__global__ __launch_bounds__(64 * lane_waves(NBLK)) void lane_chain_kernel(ChainArgs a, int meet_only) {
+__global__ __launch_bounds__(64 * lane_waves(NBLK)) void lane_chain_kernel(ChainArgs a, int meet_only, int poll_limit) {
     using S = LaneShape<NBLK>;
     constexpr int kLaneWaves = lane_waves(NBLK);
     extern __shared__ __attribute__((aligned(16))) unsigned char lane_smem[];
@@ -537,10 +536,10 @@ __global__ __launch_bounds__(64 * lane_waves(NBLK)) void lane_chain_kernel(Chain
     __syncthreads();
     if (wv == 0) {
         __builtin_amdgcn_s_setprio(3);
-        lane_chain_wave<NBLK, TIN, PASS2>(a, jb, sh, lz2, feasible, meet_only);
+        lane_chain_wave<NBLK, TIN, PASS2>(a, jb, sh, lz2, feasible, meet_only, poll_limit);
     } else {
         if (PASS2 && wv == 4) clear_edgeless(4 * 64, 64);  // (the producer that shares the chain's SIMD)
-        lane_producer_wave<NBLK, TIN, PASS2>(a, jb, sh, wv - 1, lz2, meet_only);
+        lane_producer_wave<NBLK, TIN, PASS2>(a, jb, sh, wv - 1, lz2, meet_only, poll_limit);
     }
 }
 
@@ -549,30 +548,30 @@ __global__ __launch_bounds__(64 * lane_waves(NBLK)) void lane_chain_kernel(Chain
 bool lane_supported(int T) { return T >= 8 && T <= 64 && T % 4 == 0; }
 
 template <int NBLK, typename TIN, bool PASS2>
-static hipError_t launch_lane_kernel(const ChainArgs& a, int meet_only, hipStream_t st) {
+static hipError_t launch_lane_kernel(const ChainArgs& a, int meet_only, int poll_limit, hipStream_t st) {
     const size_t bytes = sizeof(LaneShared<NBLK>);
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&lane_chain_kernel<NBLK, TIN, PASS2>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL((lane_chain_kernel<NBLK, TIN, PASS2>), dim3(2 * a.B), dim3(64 * lane_waves(NBLK)), bytes, st, a, meet_only);
+    hipLaunchKernelGGL((lane_chain_kernel<NBLK, TIN, PASS2>), dim3(2 * a.B), dim3(64 * lane_waves(NBLK)), bytes, st, a, meet_only, poll_limit);
     return hipGetLastError();
 }
 template <int NBLK>
-static hipError_t launch_lane_nblk(bool second_pass, int dtype, const ChainArgs& a, int meet_only, hipStream_t st) {
+static hipError_t launch_lane_nblk(bool second_pass, int dtype, const ChainArgs& a, int meet_only, int poll_limit, hipStream_t st) {
     if (dtype == 0)
-        return second_pass ? launch_lane_kernel<NBLK, float, true>(a, meet_only, st)
-                           : launch_lane_kernel<NBLK, float, false>(a, meet_only, st);
-    return second_pass ? launch_lane_kernel<NBLK, uint16_t, true>(a, meet_only, st)
-                       : launch_lane_kernel<NBLK, uint16_t, false>(a, meet_only, st);
+        return second_pass ? launch_lane_kernel<NBLK, float, true>(a, meet_only, poll_limit, st)
+                           : launch_lane_kernel<NBLK, float, false>(a, meet_only, poll_limit, st);
+    return second_pass ? launch_lane_kernel<NBLK, uint16_t, true>(a, meet_only, poll_limit, st)
+                       : launch_lane_kernel<NBLK, uint16_t, false>(a, meet_only, poll_limit, st);
 }
 
-hipError_t launch_lane_pass(bool second_pass, int dtype, const ChainArgs& a, bool meet_only, hipStream_t st) {
+hipError_t launch_lane_pass(bool second_pass, int dtype, const ChainArgs& a, bool meet_only, int poll_limit, hipStream_t st) {
     if (!lane_supported(a.T) || a.chunk > 0 || a.emit) return hipErrorInvalidValue;
     const int mo = meet_only ? 1 : 0;
-    if (a.T <= 16) return launch_lane_nblk<1>(second_pass, dtype, a, mo, st);
-    if (a.T <= 32) return launch_lane_nblk<2>(second_pass, dtype, a, mo, st);
-    if (a.T <= 48) return launch_lane_nblk<3>(second_pass, dtype, a, mo, st);
-    return launch_lane_nblk<4>(second_pass, dtype, a, mo, st);
+    if (a.T <= 16) return launch_lane_nblk<1>(second_pass, dtype, a, mo, poll_limit, st);
+    if (a.T <= 32) return launch_lane_nblk<2>(second_pass, dtype, a, mo, poll_limit, st);
+    if (a.T <= 48) return launch_lane_nblk<3>(second_pass, dtype, a, mo, poll_limit, st);
+    return launch_lane_nblk<4>(second_pass, dtype, a, mo, poll_limit, st);
 }
 
 }  // namespace lccrf

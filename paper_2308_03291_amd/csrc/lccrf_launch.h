@@ -21,8 +21,9 @@ hipError_t launch_sequential_sum(int op, int dtype, const void* phi, const int32
                                  hipStream_t st, hipEvent_t between = nullptr, bool exact_only = false,
                                  unsigned long long* mail = nullptr, int* failed = nullptr, double* logZ64 = nullptr,
                                  const float* emit = nullptr, const float* trans = nullptr, int pair_poll_limit = 0,
-                                 int cus = 0, bool lanes = false);
-// lanes: the chain-wave / producer-wave kernels of lccrf_lane.hip (lane_chains_supported(T), plain potentials).
+                                 int cus = 0, bool lanes = false, int lane_poll_limit = 1 << 16);
+// lanes: the chain-wave / producer-wave kernels of lccrf_lane.hip (lane_chains_supported(T), plain potentials);
+// lane_poll_limit: polls their chain wave spends on a late matrix before it continues in the log domain.
 bool lane_chains_supported(int T);
 // Sampling (lccrf_chain.hip, lccrf_extras.hip): forward chains over whole sequences with every alpha
 // stored, then the backward sweep that draws the tags from the given uniforms [B][N].

@@ -105,6 +105,8 @@ def test_tuning_knobs_check_their_range(lib):
     assert lib.lccrf_set_scan_chunk(0) == 0
     assert lib.lccrf_set_pair_poll_limit(-2) == -1 and lib.lccrf_set_pair_poll_limit((1 << 24) + 1) == -1
     assert lib.lccrf_set_pair_poll_limit(0) == 0 and lib.lccrf_set_pair_poll_limit(-1) == 0
+    assert lib.lccrf_set_lane_poll_limit(-2) == -1 and lib.lccrf_set_lane_poll_limit((1 << 24) + 1) == -1
+    assert lib.lccrf_set_lane_poll_limit(0) == 0 and lib.lccrf_set_lane_poll_limit(-1) == 0
     # the chunk enters the workspace size: a call sized under one setting is refused under a larger need
     small = binding.workspace_bytes(binding.OP_MARGINALS, 2, 4096, 16, 0)
     assert lib.lccrf_set_scan_chunk(4) == 0

@@ -106,6 +106,27 @@ def test_lanes_peaked_long_chain_bf16(crf, oracle_mod):
                queries=("logz", "mu"))
 
 
+@pytest.mark.parametrize("polls", (0, 1, 3, 40))
+def test_lanes_chain_that_stops_waiting_finishes_in_the_log_domain(crf, oracle_mod, polls):
+    """The bounded wait of the chain wave, made to expire from the host: with a limit of 0 looks nearly every
+    chain leaves the fast path at its first position, with a few looks some leave it in the middle of a chain
+    (wherever a producer happens to be late); every result still equals the oracle's, and every kernel ends."""
+    crf.set_lane_poll_limit(polls)
+    try:
+        for T, N in ((16, 50), (32, 70), (48, 40), (64, 33)):
+            phi, lens = workloads.random_case(9800 + T + polls, 5, N, T, scale=1.5, ragged=True, min_len=1)
+            check_case(crf, oracle_mod, phi, lens, algo=crf.ALGO_SEQUENTIAL_LANES,
+                       what=f"lanes poll limit {polls} T={T}", queries=("logz", "mu"))
+    finally:
+        crf.set_lane_poll_limit(-1)
+
+
+def test_lanes_more_sequences_than_compute_units(crf, oracle_mod):
+    """Several workgroups a compute unit (and more than one round of them): 700 short sequences."""
+    phi, lens = workloads.random_case(9900, 700, 12, 32, scale=1.0, ragged=True, min_len=0)
+    check_case(crf, oracle_mod, phi, lens, algo=crf.ALGO_SEQUENTIAL_LANES, what="lanes B=700", queries=("logz", "mu"))
+
+
 def test_lanes_refuses_what_it_does_not_serve(crf):
     dev = torch.device("cuda:0")
     for T in (5, 18, 68, 128):
