@@ -11,21 +11,25 @@
 // the source values arriving by DPP row rotation (v_fmac_f32_dpp row_ror:n), the blocks by the gfx950
 // permlane swaps; no exponential, no logarithm and no reduction tree on the dependent path.  The matrix
 // entries a lane needs, in the order its rotations consume them, wait in LDS: the other waves of the
-// workgroup ("producers") load the potentials (coalesced 16-byte loads, several matrices in flight a
-// wave), exponentiate them and scatter them into a ring of LDS slots in that rotated order.  In the second
-// pass a producer keeps its matrix in registers until the chain has published the vector that entered the
-// step, and writes the marginals mu = V(s) E(s,t) G(t) of that position itself (coalesced 16-byte stores).
-// The waves meet only through flags in LDS (ready / done / stop), never at a barrier.
+// workgroup ("producers") load the potentials (coalesced 16-byte loads, the next matrix of a wave in flight
+// while it works on the current one), exponentiate them and scatter them into a ring of LDS slots in that
+// rotated order.  A producer then waits for the chain to accept the step its matrix belongs to and does the
+// step's stores: in the first pass the resulting vector (base-2 logarithms plus a double offset, the format of
+// the other sum-product kernels, so either pass may be combined with theirs), in the second pass the marginals
+// mu = V(s) E(s,t) G(t) of that position from the matrix it still holds in registers (coalesced 16-byte
+// stores).  The waves meet only through words in LDS (ready / done / stop), never at a barrier.
 //
-// Vectors are kept as V 2^O with V's maximum in [1/2, 1) (an exact power-of-two rescale after every step) and O a
-// double.  A step is accepted only if every sum lies in [2^-60, 2^60] (kSumLo, kSumHi): then whatever
-// underflowed in it is below 2^-66 of the sum it belongs to, for every entry separately, so the loss does not
-// compound from step to step.  Hard zeros (potentials of -inf), sums out of range and a producer that
-// does not show up within the poll limit send the chain wave into the log-domain tail: from that
-// position on it runs the textbook recursion alone, every log-sum-exp shifted by its own maximum, straight
-// from memory; the producers see `stop` and leave.  Both forms store the vectors in the format of the other
-// sum-product kernels (base-2 logarithms plus a double offset per position), so either pass may be combined
-// with theirs.
+// Vectors are kept as V 2^O with O = O0 + an integer: every matrix is shifted by an integer m, and after every
+// step the vector is rescaled by the power of two that brings tag 0's entry into [1/2, 1) (any accepted entry
+// serves as the reference; lane 0's comes without a reduction).  A step is accepted only if every sum lies in
+// [2^-60, 2^60] (kSumLo, kSumHi): then whatever underflowed in it is below 2^-66 of the sum it belongs to, for
+// every entry separately, so the loss does not compound from step to step.  A step that is not accepted (a
+// hard zero from a potential of -inf, entries of one matrix hundreds of bits apart) is taken by the chain wave
+// itself in the log domain, straight from memory, every log-sum-exp shifted by its own maximum, stores and
+// marginals included; the fast path resumes as soon as the vector is one that scaled single precision holds
+// faithfully again.  Eight such steps in a row, or a producer that does not deliver within the poll limit,
+// send the chain wave into the log-domain tail for the rest of its half chain; the producers see `stop` and
+// leave.
 #include "lccrf_chain_args.h"
 #include "lccrf_device.h"
 #include "lccrf_launch.h"
@@ -57,7 +61,8 @@ struct LaneShared {
     float E[S::RING][S::U + 1][S::RS];  // E[slot][u][16 b + n] = the entry lane u multiplies with rotation n of block b
                                         // (row U stays zero: read by the lanes of the chain wave that hold no tag)
     float V[kLaneVecRing][64];      // V_q, the vector that enters step q, at [q % kLaneVecRing]
-    int VOi[kLaneVecRing];          // its offset less O0 (the shifts and rescales so far: an integer)
+    int VOi[kLaneVecRing];          // twice its offset less O0 (the shifts and rescales so far: an integer), plus 1
+                                    // if the step that produced it was taken in the log domain by the chain wave
     double O0;                      // offset of V_0
     float G[kLaneMaxProducers][64]; // per producer wave: the factors of the stored vector of the other chain
     unsigned long long ready[S::RING];  // once the matrix of step q sits in slot q % RING: q + 1 in the high word,
@@ -121,56 +126,64 @@ __device__ __forceinline__ float phi2_at(const TIN* phib, size_t TT, int T, int 
     return Elem<TIN>::get(phib + (size_t)i * TT + (size_t)s * T + t) * kLog2e;
 }
 
-// The log-domain tail: steps q0 .. count - 1 of the job by the chain wave alone.  lv: the vector that enters
-// step q0, base-2 logarithms, lane = tag (-inf from T on); O its offset.  Returns with lv / O the last vector.
+// One position in the log domain by the chain wave alone, straight from memory: every log-sum-exp shifted by
+// its own maximum.  lv: the vector that enters step q, base-2 logarithms, lane = tag (-inf from T on), O its
+// offset; on return lv is the result less the integer shift that is returned (its maximum then lies in (-1, 0]).
+// Writes what the step owes to memory: the marginals of its position (second pass), the stored vector (first).
 template <typename TIN, bool PASS2>
-__device__ __forceinline__ void lane_log_tail(const ChainArgs& a, const LaneJob& jb, int q0, float& lv, double& O,
-                                              double lz2, int meet_only) {
+__device__ __forceinline__ int lane_log_step(const ChainArgs& a, const LaneJob& jb, int q, float& lv, double O,
+                                             double lz2, int meet_only) {
     const int lane = threadIdx.x & 63, T = a.T, N = a.N, b = jb.b;
     const size_t TT = (size_t)T * T;
     const TIN* phib = static_cast<const TIN*>(a.phi) + (size_t)b * N * TT;
     const size_t vb = (size_t)b * N;
-    for (int q = q0; q < jb.count; ++q) {
-        const int i = jb.first + q * jb.sdir;
-        const bool on = lane < T;
-        const int me = on ? lane : 0;
-        float other = LCCRF_NEG_INF, K = 0.f;
-        float* mu_i = nullptr;
-        if (PASS2) {
-            // forward: beta_i(t) and its offset; backward: alpha_{i-1}(s) and its offset
-            const size_t vp = jb.dir == 0 ? vb + i : vb + i - 1;
-            other = on ? (jb.dir == 0 ? a.ub : a.ua)[vp * T + me] : LCCRF_NEG_INF;
-            K = (float)(O + (jb.dir == 0 ? a.Ob : a.Oa)[vp] - lz2);
-            mu_i = a.mu + (vb + i) * TT;
-        }
-        float mx = LCCRF_NEG_INF;
-        for (int v = 0; v < T; ++v) {
-            const float x = lane_value(lv, v) + (jb.dir == 0 ? phi2_at(phib, TT, T, i, v, me) : phi2_at(phib, TT, T, i, me, v));
-            mx = fmaxf(mx, x);
-        }
-        const float g = finite_or_zero(mx);
-        float sum = 0.f;
-        for (int v = 0; v < T; ++v) {
-            const float x = lane_value(lv, v) + (jb.dir == 0 ? phi2_at(phib, TT, T, i, v, me) : phi2_at(phib, TT, T, i, me, v));
-            sum += ex2(x - g);
-            if (PASS2 && on) {
-                const float m = ex2(x + other + K);
-                if (jb.dir == 0) mu_i[(size_t)v * T + lane] = m;
-                else mu_i[(size_t)lane * T + v] = m;
-            }
-        }
-        const float r = on ? mx + lg2(sum) : LCCRF_NEG_INF;
-        const float d = finite_or_zero(xor_max<1, 64>(r));
-        lv = r - d;
-        O += (double)d;
-        if (!PASS2) {
-            const int pos = jb.dir == 0 ? i : i - 1;
-            if (!meet_only || pos == jb.h) {
-                if (on) (jb.dir == 0 ? a.ua : a.ub)[(vb + pos) * T + lane] = lv;
-                if (lane == 0) (jb.dir == 0 ? a.Oa : a.Ob)[vb + pos] = O;
-            }
+    const int i = jb.first + q * jb.sdir;
+    const bool on = lane < T;
+    const int me = on ? lane : 0;
+    float other = LCCRF_NEG_INF, K = 0.f;
+    float* mu_i = nullptr;
+    if (PASS2) {
+        // forward: beta_i(t) and its offset; backward: alpha_{i-1}(s) and its offset
+        const size_t vp = jb.dir == 0 ? vb + i : vb + i - 1;
+        other = on ? (jb.dir == 0 ? a.ub : a.ua)[vp * T + me] : LCCRF_NEG_INF;
+        K = (float)(O + (jb.dir == 0 ? a.Ob : a.Oa)[vp] - lz2);
+        mu_i = a.mu + (vb + i) * TT;
+    }
+    float mx = LCCRF_NEG_INF;
+    for (int v = 0; v < T; ++v) {
+        const float x = lane_value(lv, v) + (jb.dir == 0 ? phi2_at(phib, TT, T, i, v, me) : phi2_at(phib, TT, T, i, me, v));
+        mx = fmaxf(mx, x);
+    }
+    const float g = finite_or_zero(mx);
+    float sum = 0.f;
+    for (int v = 0; v < T; ++v) {
+        const float x = lane_value(lv, v) + (jb.dir == 0 ? phi2_at(phib, TT, T, i, v, me) : phi2_at(phib, TT, T, i, me, v));
+        sum += ex2(x - g);
+        if (PASS2 && on) {
+            const float m = ex2(x + other + K);
+            if (jb.dir == 0) mu_i[(size_t)v * T + lane] = m;
+            else mu_i[(size_t)lane * T + v] = m;
         }
     }
+    const float r = on ? mx + lg2(sum) : LCCRF_NEG_INF;
+    // an integer shift, clamped far inside the range of an int: the offsets stay O0 plus an integer
+    const float d = fminf(fmaxf(ceilf(finite_or_zero(xor_max<1, 64>(r))), -0x1p30f), 0x1p30f);
+    lv = r - d;
+    if (!PASS2) {
+        const int pos = jb.dir == 0 ? i : i - 1;
+        if (!meet_only || pos == jb.h) {
+            if (on) (jb.dir == 0 ? a.ua : a.ub)[(vb + pos) * T + lane] = lv;
+            if (lane == 0) (jb.dir == 0 ? a.Oa : a.Ob)[vb + pos] = O + (double)d;
+        }
+    }
+    return __builtin_amdgcn_readfirstlane((int)d);  // (the same in every lane; said so, it stays in a scalar register)
+}
+
+// The log-domain tail: steps q0 .. count - 1 of the job.  Returns with lv / O the last vector.
+template <typename TIN, bool PASS2>
+__device__ __forceinline__ void lane_log_tail(const ChainArgs& a, const LaneJob& jb, int q0, float& lv, double& O,
+                                              double lz2, int meet_only) {
+    for (int q = q0; q < jb.count; ++q) O += (double)lane_log_step<TIN, PASS2>(a, jb, q, lv, O, lz2, meet_only);
 }
 
 // The chain wave.
@@ -222,7 +235,8 @@ __device__ __forceinline__ void lane_chain_wave(const ChainArgs& a, const LaneJo
     const unsigned long long onmask = __builtin_amdgcn_ballot_w64(on);
     unsigned q = 0;
     const unsigned count = (unsigned)jb.count;
-    bool tail = false;
+    bool tail = false, carried = false;
+    float lv_carry = LCCRF_NEG_INF;  // the vector in logarithms, where the log-domain steps leave it to the tail
     // The matrix of a step: the entries of this lane in the order its rotations consume them, and the shift.
     constexpr int NB = kSplit ? 1 : NBLK;  // blocks of sixteen source tags a lane sums over
     struct Tile {
@@ -249,11 +263,46 @@ __device__ __forceinline__ void lane_chain_wave(const ChainArgs& a, const LaneJo
         read_tile(step, t, word);
         return true;
     };
+    // Steps that the fast path does not accept (a sum out of range: entries of one matrix hundreds of bits
+    // apart, or a hard zero) are taken in the log domain by this wave itself, one position at a time, until the
+    // vector is again one that scaled single precision holds faithfully (every entry an exact zero or within
+    // 2^-60 of the largest): then the fast path resumes with the next matrix.  The producers are told through
+    // the low bit of the published offset to leave those positions alone.  After eight such steps in a row
+    // (hard constraints throughout) the chain gives the producers up for good.
+    // 0: go on (the matrix of step q is in `nxt`), 2: it did not come, 3: that was the last step, 4: give up.
+    const auto slow_steps = [&](Tile& nxt) -> int {
+        float lvs = lane < T ? lg2(V) : LCCRF_NEG_INF;
+        for (int n = 0;; ++n) {
+            const int d = lane_log_step<TIN, PASS2>(a, jb, (int)q, lvs, O0 + (double)Oi, lz2, meet_only);
+            Oi += d;
+            float lall = lvs;  // every copy of the vector gets its tag's value
+            if constexpr (kSplit) {
+                const auto h = __builtin_amdgcn_permlane32_swap(__float_as_int(lvs), __float_as_int(lvs), false, false);
+                lall = __int_as_float(h[0]);
+            }
+            V = on ? ex2(lall) : 0.f;
+            ++q;
+            sh.V[q % kLaneVecRing][u] = V;
+            sh.VOi[q % kLaneVecRing] = (Oi << 1) | 1;
+            lds_store_release(&sh.done, (int)q);
+            if (q == count) return 3;
+            const bool faithful = !(lane < T) || lvs == LCCRF_NEG_INF || lvs >= -60.f;
+            const bool inside = (unsigned)(Oi + (1 << 28)) < (1u << 29);
+            if (__builtin_amdgcn_ballot_w64(!faithful) == 0 && inside) break;
+            if (n >= 7 || !inside) {
+                lv_carry = lvs;
+                carried = true;
+                return 4;
+            }
+        }
+        return fetch(q, nxt) ? 0 : 2;
+    };
     // One step from the matrix in `cur`; meanwhile the matrix of the next step is read into `nxt` if it is
     // already there (one look at its flag, early enough that the answer is back when the products are done),
     // else waited for at the end.  Everything the step leaves behind for the other waves is the vector, one
     // integer and the step count in LDS: the stores to memory are theirs.
-    // 0: go on, 1: the step was not accepted, 2: the next matrix did not come, 3: that was the last step.
+    // 0: go on, 1: the step was not accepted (q and the vector are unchanged), 2: the next matrix did not come,
+    // 3: that was the last step.
     // (Flags and offsets are written by every lane, the same value to the same address: cheaper for a lone
     // wave than masking the write down to one lane.)
     const auto step = [&](const Tile& cur, Tile& nxt) __attribute__((always_inline)) -> int {
@@ -285,7 +334,7 @@ __device__ __forceinline__ void lane_chain_wave(const ChainArgs& a, const LaneJo
         const int Onew = Oi + cur.m;
         // accepted: every sum in range, and the integer offset far from overflow
         const unsigned long long inr = __builtin_amdgcn_ballot_w64(sum_in_range(Ssum));
-        if ((inr & onmask) != onmask || (unsigned)(Onew + (1 << 29)) >= (1u << 30)) return 1;
+        if ((inr & onmask) != onmask || (unsigned)(Onew + (1 << 28)) >= (1u << 29)) return 1;
         // Rescale by the power of two that brings tag 0 into [1/2, 1): any accepted entry serves as the
         // reference (what bounds the vector is the range test above, not where its largest entry lies), and
         // lane 0's comes without a reduction over the lanes.  Lanes without a tag hold an exact zero.
@@ -294,7 +343,7 @@ __device__ __forceinline__ void lane_chain_wave(const ChainArgs& a, const LaneJo
         Oi = Onew + k;
         ++q;
         sh.V[q % kLaneVecRing][u] = V;
-        sh.VOi[q % kLaneVecRing] = Oi;
+        sh.VOi[q % kLaneVecRing] = Oi << 1;
         lds_store_release(&sh.done, (int)q);
         if (q == count) return 3;
         if ((unsigned)__builtin_amdgcn_readfirstlane((int)(word_next >> 32)) >= q + 1) read_tile(q, nxt, word_next);
@@ -304,16 +353,20 @@ __device__ __forceinline__ void lane_chain_wave(const ChainArgs& a, const LaneJo
     Tile tA, tB;
     if (count > 0) {
         int why = fetch(0, tA) ? 0 : 2;
-        while (why == 0) {
-            why = step(tA, tB);
-            if (why != 0) break;
-            why = step(tB, tA);
+        for (;;) {
+            while (why == 0) {
+                why = step(tA, tB);
+                if (why != 0) break;
+                why = step(tB, tA);
+            }
+            if (why != 1) break;
+            why = slow_steps(tA);  // (outside the loop of the fast path, which stays as tight as it was)
         }
         tail = why != 3;
     }
     O = O0 + (double)Oi;
     on = lane < T;  // from here on lane = tag again (the first copy)
-    lv = on ? lg2(V) : LCCRF_NEG_INF;
+    lv = !on ? LCCRF_NEG_INF : carried ? lv_carry : lg2(V);
     if (tail) {
         if (lane == 0) lds_store_release(&sh.stop, (int)q);
         lane_log_tail<TIN, PASS2>(a, jb, (int)q, lv, O, lz2, meet_only);
@@ -419,7 +472,8 @@ __device__ __forceinline__ void lane_producer_wave(const ChainArgs& a, const Lan
         if (PASS2) {
             // the chain has accepted step q: V_q and this matrix make the marginals of position i
             if (!wait_for(&sh.done, q + 1, q)) return false;
-            const double Oq = sh.O0 + (double)sh.VOi[q % kLaneVecRing];
+            if (sh.VOi[(q + 1) % kLaneVecRing] & 1) return true;  // (the chain wave took this step itself)
+            const double Oq = sh.O0 + (double)(sh.VOi[q % kLaneVecRing] >> 1);
             const float c = (float)(Oq + (double)sh_m + oo[p] - lz2);
             sh.G[w][lane] = lane < T ? ex2(aux[p] + c) : 0.f;
             const float* rowf = jb.dir == 0 ? sh.V[q % kLaneVecRing] : sh.G[w];
@@ -439,9 +493,11 @@ __device__ __forceinline__ void lane_producer_wave(const ChainArgs& a, const Lan
             // the chain has accepted step q: its result is the vector of position i (forward) or i - 1 (backward)
             if (!wait_for(&sh.done, q + 1, q)) return false;
             const int pos = jb.dir == 0 ? i : i - 1;
+            const int word = sh.VOi[(q + 1) % kLaneVecRing];
+            if (word & 1) return true;  // (the chain wave took this step itself, stores included)
             const float v = sh.V[(q + 1) % kLaneVecRing][lane];
             if (lane < T) (jb.dir == 0 ? a.ua : a.ub)[(vb + pos) * T + lane] = lg2(v);
-            if (lane == 0) (jb.dir == 0 ? a.Oa : a.Ob)[vb + pos] = sh.O0 + (double)sh.VOi[(q + 1) % kLaneVecRing];
+            if (lane == 0) (jb.dir == 0 ? a.Oa : a.Ob)[vb + pos] = sh.O0 + (double)(word >> 1);
         }
         return true;
     };

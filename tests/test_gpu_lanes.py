@@ -78,7 +78,8 @@ def test_lanes_scale_jumps(crf, oracle_mod, T, N):
 @pytest.mark.parametrize("T", (16, 48))
 def test_lanes_wide_range_inside_a_matrix(crf, oracle_mod, T):
     """Entries of one matrix hundreds of nats apart: sums fall below the accepted range somewhere in the
-    chain, and the rest of that half chain runs in the log domain (both directions, both passes)."""
+    chain; those positions are taken in the log domain by the chain wave, and the fast path resumes once the
+    vector fits scaled single precision again (both directions, both passes)."""
     N = 40
     phi, _ = workloads.random_case(9500 + T, 4, N, T, scale=1.0)
     phi[0, 7, : T // 2, :] -= 200.0
@@ -100,7 +101,7 @@ def test_lanes_large_offset(crf, oracle_mod):
 
 def test_lanes_peaked_long_chain_bf16(crf, oracle_mod):
     """The value distribution of the long-sequence configuration (bfloat16, ten times a standard normal)
-    over a shorter chain: positions drop into the log-domain tail wherever the peaked matrices starve a tag."""
+    over a shorter chain: single positions drop into the log domain wherever the peaked matrices starve a tag."""
     phi, _ = workloads.random_case(9700, 2, 600, 16, scale=10.0, dtype="bf16")
     check_case(crf, oracle_mod, phi, None, poison=False, algo=crf.ALGO_SEQUENTIAL_LANES, what="lanes peaked bf16",
                queries=("logz", "mu"))
