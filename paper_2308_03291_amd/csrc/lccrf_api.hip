@@ -238,6 +238,12 @@ inline bool lanes_pay_sum(int op, int B, int N, int T) {
     return T <= 48 || op == 0;
 }
 
+// Whether the max-plus chains go to the chain-wave kernels (lccrf_lane_max.hip) under AUTO.
+inline bool lanes_pay_max(int B, int N, int T) {
+    (void)B; (void)N; (void)T;
+    return false;  // (until measured)
+}
+
 int sum_query(int op, const void* phi, int dt, const int32_t* lengths, int B, int N, int T, float* logZ,
               float* marginals, void* workspace, size_t workspace_bytes, void* stream, int algo,
               void* ev_begin = nullptr, void* ev_between = nullptr, void* ev_end = nullptr) {
@@ -359,7 +365,7 @@ int lccrf_argmax_algo(const void* phi, lccrf_dtype dt, const int32_t* lengths, i
     if (!aligned_to(tags, 4) || (best_score && !aligned_to(best_score, 4))) return LCCRF_EALIGN;
     if (lengths && !aligned_to(lengths, 4)) return LCCRF_EALIGN;
     if (algo == LCCRF_ALGO_SCAN && !lccrf::scan_supported_max(T)) return LCCRF_ENOTIMPL;
-    if (algo == LCCRF_ALGO_SEQUENTIAL_LANES) return LCCRF_ENOTIMPL;  // (a sum-product schedule)
+    if (algo == LCCRF_ALGO_SEQUENTIAL_LANES && !lccrf::lane_max_supported(T)) return LCCRF_ENOTIMPL;
     const MaxWorkspace w = max_workspace(B, N, T);
     char* base = static_cast<char*>(workspace);
     hipStream_t st = static_cast<hipStream_t>(stream);
@@ -376,7 +382,9 @@ int lccrf_argmax_algo(const void* phi, lccrf_dtype dt, const int32_t* lengths, i
         if (e == hipSuccess)
             e = lccrf::launch_chunked_max(dt, phi, lengths, B, N, T, bp, mid, tags, scan_chunk(B, N, T), pin, st);
     } else {
-        e = lccrf::launch_sequential_max(dt, phi, lengths, B, N, T, bp, mid, best_score, tags, st);
+        const bool lanes = algo == LCCRF_ALGO_SEQUENTIAL_LANES || (algo == LCCRF_ALGO_AUTO && lanes_pay_max(B, N, T));
+        e = lccrf::launch_sequential_max(dt, phi, lengths, B, N, T, bp, mid, best_score, tags, st, lanes,
+                                         g_lane_poll_limit.load(std::memory_order_relaxed));
     }
     return e == hipSuccess ? LCCRF_OK : LCCRF_ELAUNCH;
 }

@@ -1,0 +1,483 @@
+// Max-plus (Viterbi) chains for up to 64 tags with the recursion taken off everything else: one wave of a
+// workgroup runs the chain of scores, the others stream the potentials and find the pointers.
+//
+// The recursion of section "Computing Most Probable Structure" (the forward algorithm with max in place of
+// log-sum-exp), delta_i(t) = max_s delta_{i-1}(s) + phi_i(s, t), is a chain of n dependent steps, and in
+// the one-wave and four-wave kernels of lccrf_viterbi.hip a step carries everything: the loads' conversion
+// to double precision, the additions, and a tournament in which every comparison moves a score AND the tag
+// it came from (a compare and three selects where a plain maximum is one instruction).  Only the scores are
+// on the chain of dependencies: the pointer of position i needs delta_{i-1}, nothing needs the pointer
+// before the trace.  So, as in the sum-product kernels of lccrf_lane.hip:
+//
+//   chain wave (wave 0):  out(x) = max_y in(y) + M(y, x) in double precision, v_add_f64 and v_max_f64 only,
+//       M read from LDS as doubles in the order its lanes consume them, the vector published in LDS;
+//   helper waves (1 .. 7): each takes every seventh position: loads the matrix (the next one in flight
+//       while it works on the current one), converts it and hands it to the chain wave through a ring of LDS
+//       slots, then, as soon as the vector that enters the position is published, finds the pointers
+//       (smallest best source tag, the tie rule of the other kernels) from the matrix it still holds in
+//       registers and stores them.
+//
+// Forward and backward chains differ only in how a helper reads the matrix: M(y, x) = phi_i(y, x) for the
+// forward chain (delta), phi_i(x, y) for the backward one (eps), y the tag the vector comes in on.  Lane
+// part * TP + x of a wave works on column x and the RPL source tags from part * RPL on.
+//
+// Scores are sums in double precision of the same operands as in the other kernels and the oracle, a maximum
+// is exact, and the pointer is the smallest tag that attains it: results are bit-identical whichever kernel
+// ran.  The waves meet through words in LDS (ready / done / stop), never at a barrier; every wait is bounded:
+// a chain wave whose matrix does not come within the poll limit goes on alone (loads, scores and pointers,
+// a position at a time), tells the helpers through `stop`, and they leave.
+#include "lccrf_chain_args.h"
+#include "lccrf_device.h"
+#include "lccrf_launch.h"
+#include "lccrf_lds_flags.h"
+#include "lccrf_viterbi_args.h"
+
+#include <type_traits>
+
+namespace lccrf {
+
+constexpr int kMaxWaves = 8;      // wave 0 runs the chain, the others are helpers
+constexpr int kMaxHelpers = kMaxWaves - 1;
+constexpr int kMaxVecRing = 16;   // published vectors kept (the chain leads a helper by fewer than that)
+
+// TP: padded tag count (lanes per copy of the columns), ROWS: source tags covered (TP, or 48 of 64).
+template <int TP, int ROWS>
+struct MaxShape {
+    static_assert(TP == 16 || TP == 32 || TP == 64, "16, 32 or 64 columns");
+    static_assert(ROWS % 16 == 0 && ROWS <= TP && (ROWS == TP || TP == 64), "rows in blocks of sixteen");
+    static constexpr int P = 64 / TP;       // lanes that share a column
+    static constexpr int RPL = ROWS / P;    // source tags a lane works on: 4, 16, 48 or 64
+    static constexpr int CH = RPL < 16 ? RPL : 16;  // ... in pieces of this many
+    static constexpr int RING = TP < 64 ? 8 : ROWS == 48 ? 6 : 4;  // LDS slots for matrices
+    static constexpr int NG = RPL / 4;      // 16-byte pieces of a matrix a helper lane loads
+    static constexpr bool PRELOAD = TP <= 32;  // the chain wave holds the next matrix in registers
+    static_assert(kMaxHelpers + 1 < kMaxVecRing, "a helper reads its vector before the chain can overwrite it");
+};
+
+template <int TP, int ROWS>
+struct MaxShared {
+    using S = MaxShape<TP, ROWS>;
+    double M[S::RING][S::RPL / 2][64][2];  // M[slot][k / 2][lane][k % 2]: entry k of that lane (16-byte reads, lane after lane)
+    double V[kMaxVecRing][TP];             // V_q, the vector that enters step q, at [q % kMaxVecRing]
+    double own[2][TP];                     // the vectors of a chain wave that goes on alone
+    int ready[S::RING];                    // q + 1 once the matrix of step q sits in slot q % RING
+    int kept[S::RING];                     // q + 1 once the helper of step q has read the matrix back for its pointers
+    int done;                              // steps the chain wave has finished (V_done is published)
+    int stop;                              // first step the chain wave takes alone (INT_MAX: none)
+};
+
+struct MaxJob {
+    int dir;
+    int first, sdir, count;  // step q consumes the matrix of position first + q sdir
+};
+
+// The entries of one matrix this lane works on: v[k] = M(y0 + k, x).  Addresses are clamped into the matrix;
+// what lies outside is masked when it is used (max_entry).
+template <int RPL, typename TIN>
+__device__ __forceinline__ void max_load_entries(const TIN* mat, int T, int dir, bool aligned, int y0, int x, float (&v)[RPL]) {
+    const int xc = x < T ? x : T - 1;
+    if (dir == 0) {
+#pragma unroll
+        for (int k = 0; k < RPL; ++k) v[k] = Elem<TIN>::get(mat + (size_t)(y0 + k < T ? y0 + k : T - 1) * T + xc);
+    } else {
+        const TIN* row = mat + (size_t)xc * T;
+        if (aligned) {  // T % 4 == 0: 16-byte (8-byte) pieces of the row
+#pragma unroll
+            for (int k = 0; k < RPL; k += 4) {
+                float q[4];
+                Elem<TIN>::get4(row + (y0 + k < T ? y0 + k : T - 4), q);
+                v[k] = q[0]; v[k + 1] = q[1]; v[k + 2] = q[2]; v[k + 3] = q[3];
+            }
+        } else {
+#pragma unroll
+            for (int k = 0; k < RPL; ++k) v[k] = Elem<TIN>::get(row + (y0 + k < T ? y0 + k : T - 1));
+        }
+    }
+}
+__device__ __forceinline__ double max_entry(float v, bool inside) { return (double)(inside ? v : LCCRF_NEG_INF); }
+
+// Best source tag per column: the winner of in(y) + M(y, x) over the lane's RPL source tags and then over the
+// lanes that share the column; ties to the smaller tag, kNoArg if nothing is finite.
+// A piece of CH source tags from tag ya on: vin: the vector in LDS from that tag on; entry(k): M(ya + k, x) and
+// M(ya + k + 1, x) as doubles, -inf outside the matrix.  The maximum by plain maxima (one instruction a
+// candidate), then the first candidate equal to it.
+template <int CH, typename Entry>
+__device__ __forceinline__ Best max_pointer_piece(const double* vin, int ya, Entry entry) {
+    double val[CH];
+#pragma unroll
+    for (int k2 = 0; k2 < CH / 2; ++k2) {
+        const double2 in = *reinterpret_cast<const double2*>(vin + 2 * k2);
+        const double2 m = entry(2 * k2);
+        val[2 * k2] = in.x + m.x;
+        val[2 * k2 + 1] = in.y + m.y;
+    }
+    double m[CH];
+#pragma unroll
+    for (int k = 0; k < CH; ++k) m[k] = val[k];
+#pragma unroll
+    for (int w = 1; w < CH; w <<= 1)
+#pragma unroll
+        for (int k = 0; k + w < CH; k += 2 * w) m[k] = __builtin_fmax(m[k], m[k + w]);
+    int arg = kNoArg;
+#pragma unroll
+    for (int k = CH - 1; k >= 0; --k) arg = val[k] == m[0] ? ya + k : arg;
+    return Best{m[0], m[0] == -__builtin_huge_val() ? kNoArg : arg};
+}
+template <int P>
+__device__ __forceinline__ Best max_pointer_parts(Best best) {
+    if (P >= 4) best = swap_best<16>(best);
+    if (P >= 2) best = swap_best<32>(best);
+    return best;
+}
+template <int TP, int ROWS, typename Entry>
+__device__ __forceinline__ Best max_pointer(const double* vin, int y0, Entry entry) {
+    using S = MaxShape<TP, ROWS>;
+    Best best{-__builtin_huge_val(), kNoArg};
+#pragma unroll 1
+    for (int c = 0; c < S::RPL; c += S::CH) {  // (a piece at a time: the pieces unrolled side by side would not fit the registers)
+        const Best wc = max_pointer_piece<S::CH>(vin + y0 + c, y0 + c, [&](int k) { return entry(c + k); });
+        if (wc.v > best.v) best = wc;  // ascending pieces: the first maximum stays
+    }
+    return max_pointer_parts<S::P>(best);
+}
+
+// max over the lanes that share a column (every one of them gets it)
+__device__ __forceinline__ double max_raw(double a, double b) {  // (operands that are never signalling NaNs: no quieting first)
+    double r;
+    asm("v_max_f64 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b));
+    return r;
+}
+template <int P>
+__device__ __forceinline__ double max_over_parts(double r) {
+    if (P >= 4) {
+        const long long b = __double_as_longlong(r);
+        const int lo = (int)(b & 0xffffffffll), hi = (int)(b >> 32);
+        const auto rl = __builtin_amdgcn_permlane16_swap(lo, lo, false, false);
+        const auto rh = __builtin_amdgcn_permlane16_swap(hi, hi, false, false);
+        r = max_raw(__longlong_as_double(((long long)(int)rh[0] << 32) | (unsigned int)rl[0]),
+                    __longlong_as_double(((long long)(int)rh[1] << 32) | (unsigned int)rl[1]));
+    }
+    if (P >= 2) {
+        const long long b = __double_as_longlong(r);
+        const int lo = (int)(b & 0xffffffffll), hi = (int)(b >> 32);
+        const auto rl = __builtin_amdgcn_permlane32_swap(lo, lo, false, false);
+        const auto rh = __builtin_amdgcn_permlane32_swap(hi, hi, false, false);
+        r = max_raw(__longlong_as_double(((long long)(int)rh[0] << 32) | (unsigned int)rl[0]),
+                    __longlong_as_double(((long long)(int)rh[1] << 32) | (unsigned int)rl[1]));
+    }
+    return r;
+}
+
+// The chain wave.
+template <int TP, int ROWS, typename TIN>
+__device__ __forceinline__ void max_chain_wave(const VitArgs& a, const VitSpan& sp, const MaxJob& jb, MaxShared<TP, ROWS>& sh,
+                                               double* mid, int poll_limit) {
+    using S = MaxShape<TP, ROWS>;
+    constexpr int RPL = S::RPL;
+    const int lane = threadIdx.x & 63, T = a.T;
+    const int part = lane / TP, x = lane % TP, y0 = part * RPL;
+    const unsigned count = (unsigned)jb.count;
+    unsigned q = 0;
+    struct Tile {
+        double m[S::PRELOAD ? RPL : 2];
+    };
+    const auto read_tile = [&](unsigned step, Tile& t) {
+        if constexpr (S::PRELOAD) {
+            const unsigned slot = step % S::RING;
+#pragma unroll
+            for (int k2 = 0; k2 < RPL / 2; ++k2) {
+                const double2 d = *reinterpret_cast<const double2*>(&sh.M[slot][k2][lane][0]);
+                t.m[2 * k2] = d.x;
+                t.m[2 * k2 + 1] = d.y;
+            }
+        }
+    };
+    // waits for the matrix of `step` (bounded) and reads it; false: it did not come
+    const auto fetch = [&](unsigned step, Tile& t) -> bool {
+        int spins = 0;
+        while ((unsigned)__builtin_amdgcn_readfirstlane(lds_load_acquire(&sh.ready[step % S::RING])) < step + 1)
+            if (++spins > poll_limit) return false;
+        read_tile(step, t);
+        return true;
+    };
+    // One step from the matrix in `cur` (read from LDS inside the step at 64 columns).  The matrix of the next step
+    // is read into `nxt` behind the additions, whether it is there or not, so that it comes back under the maxima;
+    // the flag that says whether it was there is looked at before, at the start of the step (LDS executes a wave's
+    // instructions in order: a flag that was up when it was read means that the reads behind it found the matrix).
+    // If it was not, the matrix is waited for at the end of the step and read again.
+    // 0: go on, 2: the next matrix did not come, 3: that was the last step.
+    const auto step = [&](const Tile& cur, Tile& nxt) __attribute__((always_inline)) -> int {
+        const double* vin = &sh.V[q % kMaxVecRing][y0];
+        const unsigned slot = q % S::RING;
+        double2 in[S::CH / 2];
+        if constexpr (S::PRELOAD) {
+#pragma unroll
+            for (int k2 = 0; k2 < S::CH / 2; ++k2) in[k2] = *reinterpret_cast<const double2*>(vin + 2 * k2);
+        }
+        const int flag_next = lds_load_acquire(&sh.ready[(q + 1) % S::RING]);
+        double r = 0.0;
+#pragma unroll
+        for (int c = 0; c < RPL; c += S::CH) {
+            double val[S::CH];
+#pragma unroll
+            for (int k2 = 0; k2 < S::CH / 2; ++k2) {
+                double m0, m1;
+                if constexpr (S::PRELOAD) {
+                    m0 = cur.m[c + 2 * k2];
+                    m1 = cur.m[c + 2 * k2 + 1];
+                } else {
+                    in[k2] = *reinterpret_cast<const double2*>(vin + c + 2 * k2);
+                    const double2 d = *reinterpret_cast<const double2*>(&sh.M[slot][c / 2 + k2][lane][0]);
+                    m0 = d.x;
+                    m1 = d.y;
+                }
+                val[2 * k2] = in[k2].x + m0;
+                val[2 * k2 + 1] = in[k2].y + m1;
+            }
+            if constexpr (S::PRELOAD) {
+                __builtin_amdgcn_sched_barrier(0);
+                read_tile(q + 1, nxt);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+#pragma unroll
+            for (int w = 1; w < S::CH; w <<= 1)
+#pragma unroll
+                for (int k = 0; k + w < S::CH; k += 2 * w) val[k] = __builtin_fmax(val[k], val[k + w]);
+            r = c == 0 ? val[0] : __builtin_fmax(r, val[0]);
+            if constexpr (!S::PRELOAD) __builtin_amdgcn_sched_barrier(0);  // (a piece at a time in the registers)
+        }
+        r = max_over_parts<S::P>(r);
+        ++q;
+        sh.V[q % kMaxVecRing][x] = r;  // (the lanes that share a column write the same value)
+        lds_store_release(&sh.done, (int)q);
+        if (q == count) return 3;
+        if ((unsigned)__builtin_amdgcn_readfirstlane(flag_next) < q + 1 && !fetch(q, nxt)) return 2;
+        return 0;
+    };
+    bool alone = false;
+    if (count > 0) {
+        Tile tA, tB;
+        int why = fetch(0, tA) ? 0 : 2;
+        while (why == 0) {
+            why = step(tA, tB);
+            if (why != 0) break;
+            why = step(tB, tA);
+        }
+        alone = why != 3;
+    }
+    const double* last = sh.V[q % kMaxVecRing];
+    if (alone) {
+        // The rest of the chain by this wave alone: loads, scores and pointers, a position at a time.  The
+        // published vectors stay as they are for the helpers that still work on earlier positions.
+        lds_store_release(&sh.stop, (int)q);
+        const size_t TT = (size_t)T * T;
+        const TIN* phib = static_cast<const TIN*>(a.phi) + (size_t)sp.b * a.N * TT;
+        uint8_t* bpb = a.bp + (size_t)sp.b * a.N * T;
+        const bool aligned = (T % 4) == 0;
+        int buf = 0;
+        sh.own[0][x] = last[x];
+        for (; q < count; ++q) {
+            const int i = jb.first + (int)q * jb.sdir;
+            Best w{-__builtin_huge_val(), kNoArg};
+#pragma unroll 1
+            for (int c = 0; c < RPL; c += S::CH) {  // (a piece of the source tags at a time: few registers)
+                float v[S::CH];
+                max_load_entries<S::CH, TIN>(phib + (size_t)i * TT, T, jb.dir, aligned, y0 + c, x, v);
+                const Best wc = max_pointer_piece<S::CH>(sh.own[buf] + y0 + c, y0 + c, [&](int k) {
+                    double2 d;
+                    d.x = max_entry(v[k], y0 + c + k < T && x < T);
+                    d.y = max_entry(v[k + 1], y0 + c + k + 1 < T && x < T);
+                    return d;
+                });
+                if (wc.v > w.v) w = wc;  // ascending pieces: the first maximum stays
+            }
+            w = max_pointer_parts<S::P>(w);
+            sh.own[buf ^ 1][x] = w.v;
+            if (part == 0 && x < T) bpb[(size_t)i * T + x] = (uint8_t)(w.a == kNoArg ? 0 : w.a);
+            buf ^= 1;
+        }
+        last = sh.own[buf];
+    }
+    if (lane < T) mid[lane] = last[lane];
+}
+
+// A helper wave.
+template <int TP, int ROWS, typename TIN>
+__device__ __forceinline__ void max_helper_wave(const VitArgs& a, const VitSpan& sp, const MaxJob& jb, MaxShared<TP, ROWS>& sh,
+                                                int w, int poll_limit) {
+    using S = MaxShape<TP, ROWS>;
+    constexpr int RPL = S::RPL, NG = S::NG, W = kMaxHelpers;
+    const int lane = threadIdx.x & 63, T = a.T;
+    const int part = lane / TP, x = lane % TP, y0 = part * RPL;
+    const int nj = w < jb.count ? (jb.count - w + W - 1) / W : 0;  // matrices of this wave: steps w, w + W, ...
+    if (nj == 0) return;
+    const size_t TT = (size_t)T * T;
+    const TIN* phib = static_cast<const TIN*>(a.phi) + (size_t)sp.b * a.N * TT;
+    uint8_t* bpb = a.bp + (size_t)sp.b * a.N * T;
+    // The matrix is loaded as it lies in memory, piece lane + 64 m of 16 bytes (row s, columns t0 .. t0 + 3), and
+    // scattered into the slot in the chain wave's order: entry (y, x) = (s, t) of a forward chain, (t, s) of a
+    // backward one, sits at M[slot][k / 2][part TP + x][k % 2] with y = part RPL + k.
+    int lidx[NG];  // index (in doubles) of the first entry of piece m in a slot
+    unsigned valid = 0;
+#pragma unroll
+    for (int m = 0; m < NG; ++m) {
+        const int off = 4 * (lane + 64 * m);
+        const bool ok = off < (int)TT;
+        valid |= ok ? (1u << m) : 0u;
+        const int s_ = (ok ? off : 0) / T, t0 = (ok ? off : 0) % T;
+        const int yy = jb.dir == 0 ? s_ : t0, xx = jb.dir == 0 ? t0 : s_;
+        const int k = yy % RPL;
+        lidx[m] = (((k >> 1) * 64 + (yy / RPL) * TP + xx) << 1) + (k & 1);
+    }
+    float raw[2][NG][4];
+    const auto load = [&](int j, int p) {
+        const int q = w + (j < nj ? j : nj - 1) * W;
+        const int i = jb.first + q * jb.sdir;
+        const TIN* mat = phib + (size_t)i * TT;
+#pragma unroll
+        for (int m = 0; m < NG; ++m) Elem<TIN>::get4(mat + (((valid >> m) & 1) ? 4 * (lane + 64 * m) : 0), raw[p][m]);
+    };
+    // Waits until the flag reaches `target` (true) or the chain wave has gone on alone at or before step `q`
+    // (false).  The chain wave always does one or the other: each of its own waits is bounded by the poll limit
+    // of the call.  The limit here is a last resort that only keeps a wave from spinning for ever.
+    const auto wait_for = [&](const int* flag, int target, int q) -> bool {
+        long long spins = 0;
+        while (lds_load_acquire(flag) < target) {
+            if (lds_load_acquire(&sh.stop) <= q || ++spins > 1000ll * (poll_limit + 65536)) return false;
+            __builtin_amdgcn_s_sleep(1);
+        }
+        return true;
+    };
+    // The pointers of a position are stored a matrix later, ahead of a wait that is long anyway: the counter that
+    // tells when loaded data has arrived counts stores as well, in order, so a store issued just before the next
+    // matrix is needed would make the wave wait for the store's acknowledgement (more than a thousand cycles).
+    uint8_t held = 0;
+    uint8_t* held_at = nullptr;
+    const auto flush = [&]() {
+        if (held_at && part == 0 && x < T) *held_at = held;
+        held_at = nullptr;
+    };
+    // One matrix (number j of this wave, in buffer p).  false: the chain wave has taken over, nothing more to do.
+    const auto process = [&](int j, auto pc) -> bool {
+        constexpr int p = decltype(pc)::value;
+        const int q = w + j * W;
+        const int i = jb.first + q * jb.sdir;
+        const int slot = q % S::RING;
+        // the slot is free once the chain wave has finished step q - RING and that step's helper has its pointers
+        if (!wait_for(&sh.done, q - S::RING + 1, q) || !wait_for(&sh.kept[slot], q - S::RING + 1, q)) return false;
+        double* Ms = &sh.M[slot][0][0][0];
+#pragma unroll
+        for (int m = 0; m < NG; ++m)
+            if ((valid >> m) & 1) {
+                if (jb.dir == 0) {  // four columns of one source tag: 16 bytes apart
+#pragma unroll
+                    for (int k = 0; k < 4; ++k) Ms[lidx[m] + 2 * k] = (double)raw[p][m][k];
+                } else {            // four source tags of one column: two pairs
+                    double2 d0, d1;
+                    d0.x = (double)raw[p][m][0]; d0.y = (double)raw[p][m][1];
+                    d1.x = (double)raw[p][m][2]; d1.y = (double)raw[p][m][3];
+                    *reinterpret_cast<double2*>(Ms + lidx[m]) = d0;
+                    *reinterpret_cast<double2*>(Ms + lidx[m] + 128) = d1;
+                }
+            }
+        if (lane == 0) lds_store_release(&sh.ready[slot], q + 1);
+        flush();
+        // the pointers of position i once the vector that enters it is published, from the matrix as it sits in the slot
+        if (!wait_for(&sh.done, q, q)) return false;
+        const Best b = max_pointer<TP, ROWS>(sh.V[q % kMaxVecRing], y0, [&](int k) {
+            return *reinterpret_cast<const double2*>(&sh.M[slot][k >> 1][lane][0]);
+        });
+        if (lane == 0) lds_store_release(&sh.kept[slot], q + 1);
+        held = (uint8_t)(b.a == kNoArg ? 0 : b.a);
+        held_at = bpb + (size_t)i * T + x;
+        return true;
+    };
+    // Two buffers: the next matrix is requested just before the current one is worked on.
+    using Buf0 = std::integral_constant<int, 0>;
+    using Buf1 = std::integral_constant<int, 1>;
+    load(0, 0);
+    for (int j = 0; j < nj; j += 2) {
+        load(j + 1, 1);
+        __builtin_amdgcn_sched_barrier(0);
+        if (!process(j, Buf0{})) break;
+        load(j + 2, 0);
+        __builtin_amdgcn_sched_barrier(0);
+        if (j + 1 < nj && !process(j + 1, Buf1{})) break;
+    }
+    flush();
+}
+
+template <int TP, int ROWS, typename TIN>
+__global__ __launch_bounds__(64 * kMaxWaves) void viterbi_lane_kernel(VitArgs a, int poll_limit) {
+    using S = MaxShape<TP, ROWS>;
+    extern __shared__ __attribute__((aligned(16))) unsigned char max_smem[];
+    MaxShared<TP, ROWS>& sh = *reinterpret_cast<MaxShared<TP, ROWS>*>(max_smem);
+    const int tid = threadIdx.x;
+    const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);  // uniform: loops over a wave's work stay scalar
+    const int dir = blockIdx.x & 1;
+    const VitSpan sp = vit_span(a, blockIdx.x >> 1);
+    if (sp.empty) return;
+    const int b = sp.b, N = a.N, T = a.T;
+    const int p0 = sp.p0, e = sp.e, h = meeting_point(p0, e);
+    MaxJob jb;
+    jb.dir = dir;
+    if (dir == 0) { jb.first = p0 + 1; jb.sdir = +1; jb.count = h - p0; }
+    else { jb.first = e; jb.sdir = -1; jb.count = e - h; }
+    double* mid = a.mid + (((size_t)b * a.C + sp.c) * 2 + dir) * T;
+    // the vector that enters step 0
+    if (tid < TP) {
+        const double ninf = -__builtin_huge_val();
+        double v0 = ninf;
+        if (tid < T) {
+            if (dir == 0) {
+                if (sp.t0 == 0) v0 = (double)Elem<TIN>::get(static_cast<const TIN*>(a.phi) + (size_t)b * N * T * T + tid);
+                else v0 = (tid == a.pin[(size_t)b * a.C + sp.c - 1]) ? 0.0 : ninf;
+            } else {
+                // a whole sequence may end in any tag; a chunk must end in its pinned tag
+                v0 = (a.chunk <= 0 || tid == a.pin[(size_t)b * a.C + sp.c]) ? 0.0 : ninf;
+            }
+        }
+        sh.V[0][tid] = v0;
+    }
+    if (tid < S::RING) { sh.ready[tid] = 0; sh.kept[tid] = 0; }
+    if (tid == 0) { sh.done = 0; sh.stop = 0x7fffffff; }
+    if (T != TP) {  // entries past the tag set: the helpers never write them
+        double* Mz = &sh.M[0][0][0][0];
+        for (int k = tid; k < S::RING * S::RPL * 64; k += 64 * kMaxWaves) Mz[k] = -__builtin_huge_val();
+    }
+    __syncthreads();
+    if (wv == 0) {
+        __builtin_amdgcn_s_setprio(3);
+        max_chain_wave<TP, ROWS, TIN>(a, sp, jb, sh, mid, poll_limit);
+    } else {
+        max_helper_wave<TP, ROWS, TIN>(a, sp, jb, sh, wv - 1, poll_limit);
+    }
+}
+
+// ---------------------------------------------------------------------------------------
+// Plain potentials, whole sequences or the chunks of the max-plus scan, up to 64 tags.
+bool lane_max_supported(int T) { return T >= 4 && T <= 64 && T % 4 == 0; }  // (16-byte pieces of a row)
+
+template <int TP, int ROWS, typename TIN>
+static hipError_t launch_max_kernel(const VitArgs& a, int poll_limit, hipStream_t st) {
+    const size_t bytes = sizeof(MaxShared<TP, ROWS>);
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&viterbi_lane_kernel<TP, ROWS, TIN>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL((viterbi_lane_kernel<TP, ROWS, TIN>), dim3(2 * a.B * a.C), dim3(64 * kMaxWaves), bytes, st, a, poll_limit);
+    return hipGetLastError();
+}
+template <typename TIN>
+static hipError_t launch_max_T(const VitArgs& a, int poll_limit, hipStream_t st) {
+    if (a.T <= 16) return launch_max_kernel<16, 16, TIN>(a, poll_limit, st);
+    if (a.T <= 32) return launch_max_kernel<32, 32, TIN>(a, poll_limit, st);
+    if (a.T <= 48) return launch_max_kernel<64, 48, TIN>(a, poll_limit, st);
+    return launch_max_kernel<64, 64, TIN>(a, poll_limit, st);
+}
+
+hipError_t launch_lane_max_chains(int dtype, const VitArgs& a, int poll_limit, hipStream_t st) {
+    if (!lane_max_supported(a.T) || a.emit) return hipErrorInvalidValue;
+    return dtype == 0 ? launch_max_T<float>(a, poll_limit, st) : launch_max_T<uint16_t>(a, poll_limit, st);
+}
+
+}  // namespace lccrf

@@ -102,8 +102,12 @@ hipError_t launch_cross_reduce(bool kl, const float* ent, const int32_t* lengths
 // Max-plus chains (two per sequence, meeting in the middle) and the trace.  bp: [B][N][T] bytes,
 // mid: viterbi_mid_doubles(B, 1, T) doubles of scratch.
 size_t viterbi_mid_doubles(int B, int C, int T);
+// lanes: the chains by a chain wave and helper waves (lccrf_lane_max.hip; lane_max_supported(T)), whose bounded
+// waits take lane_poll_limit looks.
+bool lane_max_supported(int T);
 hipError_t launch_sequential_max(int dtype, const void* phi, const int32_t* lengths, int B, int N, int T,
-                                 uint8_t* bp, double* mid, float* best_score, int32_t* tags, hipStream_t st);
+                                 uint8_t* bp, double* mid, float* best_score, int32_t* tags, hipStream_t st,
+                                 bool lanes = false, int lane_poll_limit = 1 << 16);
 
 hipError_t launch_structured_max(const float* emit, const float* trans, const int32_t* lengths, int B, int N, int T,
                                  uint8_t* bp, double* mid, float* best_score, int32_t* tags, hipStream_t st);
@@ -122,7 +126,8 @@ hipError_t launch_scan_pins(int dtype, const void* phi, const int32_t* lengths, 
 // mid: viterbi_mid_doubles(B, C, T) doubles of scratch.
 hipError_t launch_chunked_max(int dtype, const void* phi, const int32_t* lengths, int B, int N, int T, uint8_t* bp,
                               double* mid, int32_t* tags, int chunk, const int32_t* pin, hipStream_t st,
-                              const float* emit = nullptr, const float* trans = nullptr);
+                              const float* emit = nullptr, const float* trans = nullptr, bool lanes = false,
+                              int lane_poll_limit = 1 << 16);
 
 // Entropy H(p) [B] in one read of phi (lccrf_extras.hip, one-wave kernels for T <= 32).  ua / ub / Oa / Ob
 // as for launch_sequential_sum (only the rows of the meeting positions are written); ha, hb: [B][T] floats.

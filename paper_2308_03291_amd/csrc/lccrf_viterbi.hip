@@ -19,10 +19,10 @@
 #include "lccrf_chain_args.h"
 #include "lccrf_device.h"
 #include "lccrf_launch.h"
+#include "lccrf_viterbi_args.h"
 
 namespace lccrf {
 
-constexpr int kNoArg = 0x7fffffff;
 constexpr int kTraceBytes = 16384;  // LDS window of pointers walked by each trace
 
 // Forward chains at 64 < T <= 128 (T % 4 == 0) turn their tiles through LDS like the sum-product
@@ -41,50 +41,6 @@ template <typename G>
 struct VitSmem<G, true> {
     double dvec[2][G::TCAP];
 };
-
-__device__ __forceinline__ void take_better(double& v, int& a, double pv, int pa) {
-    if (pv > v || (pv == v && pa < a)) { v = pv; a = pa; }
-}
-
-struct VitArgs {
-    const void* phi;
-    const int32_t* lengths;
-    int B, N, T;
-    uint8_t* bp;   // [B][N][T] back-pointers (rows <= meeting point) and forward pointers (rows above it)
-    double* mid;   // [B][C][2][T] delta and eps at the meeting point
-    float* best_score;
-    int32_t* tags;
-    // Chunked schedule (chunk > 0): workgroup pair v serves chunk c = v % C of sequence v / C, the
-    // tag positions [c chunk, (c+1) chunk), as a chain of its own that starts one position earlier in
-    // the tag pin[b][c-1] and must end in the tag pin[b][c] (both chosen by the max-plus scan,
-    // lccrf_scan.hip); the best score is the scan's and is not written here.
-    int chunk, C;
-    const int32_t* pin;  // [B][C] tag at the last position of each chunk
-    // Structured potentials (emit non-null; float, T <= 64): phi[b][i][s][t] = trans[s][t] + emit[b][i][t].
-    const float* emit;   // [B][N][T]
-    const float* trans;  // [T][T]
-};
-
-// The stretch of positions one pair of workgroups handles.
-struct VitSpan {
-    int b, c, L;
-    int t0, t1;  // tag positions [t0, t1) whose tags this span writes (before the cut at L)
-    int p0, e;   // first and last position of the chain
-    bool empty;
-};
-__device__ __forceinline__ VitSpan vit_span(const VitArgs& a, int v) {
-    VitSpan s;
-    const bool chunked = a.chunk > 0;
-    s.b = chunked ? v / a.C : v;
-    s.c = chunked ? v % a.C : 0;
-    s.L = clamp_length(a.lengths, s.b, a.N);
-    s.t0 = chunked ? s.c * a.chunk : 0;
-    s.t1 = chunked ? (s.t0 + a.chunk < a.N ? s.t0 + a.chunk : a.N) : a.N;
-    s.empty = s.t0 >= s.L;
-    s.p0 = s.t0 > 0 ? s.t0 - 1 : 0;
-    s.e = (s.t1 < s.L ? s.t1 : s.L) - 1;
-    return s;
-}
 
 // STRUCT: potentials are trans + emit (float, T <= 128; a compile-time choice so that the dense path
 // keeps its loads free of branches).
@@ -472,18 +428,6 @@ __global__ __launch_bounds__(1024) void viterbi_stream_kernel(VitArgs a) {
     if (tid < T) mid[tid] = sm.dvec[buf][tid];
 }
 
-// The first maximum of val[0 .. n-1] (arg ascending with the index) ends in val[0] / arg[0]: a tree
-// of pairwise comparisons in which the right-hand candidate wins only if strictly greater, so the
-// chain of dependent instructions is log2 n long instead of n.
-template <int n>
-__device__ __forceinline__ void first_max_tree(double (&val)[n], int (&arg)[n]) {
-#pragma unroll
-    for (int w = 1; w < n; w <<= 1)
-#pragma unroll
-        for (int k = 0; k + w < n; k += 2 * w)
-            if (val[k + w] > val[k]) { val[k] = val[k + w]; arg[k] = arg[k + w]; }
-}
-
 // One wave per chain for T <= 32 (TP = 16 or 32 padded tags): the whole matrix of a position is spread
 // over the 64 lanes, the vector of the previous position sits in LDS, and nothing but that vector
 // crosses lanes, so a step needs no barrier between waves and no merge through LDS.
@@ -746,7 +690,13 @@ static hipError_t launch_T(const VitArgs& a, hipStream_t st) {
     return hipGetLastError();
 }
 
-static hipError_t launch_any(int dtype, const VitArgs& a, hipStream_t st) {
+static hipError_t launch_any(int dtype, const VitArgs& a, hipStream_t st, bool lanes = false, int lane_poll_limit = 0) {
+    if (lanes) {
+        const hipError_t e = launch_lane_max_chains(dtype, a, lane_poll_limit, st);
+        if (e != hipSuccess) return e;
+        hipLaunchKernelGGL(viterbi_trace_kernel, dim3(a.B * a.C), dim3(128), 0, st, a);
+        return hipGetLastError();
+    }
     const bool aligned = (a.T % 4) == 0;
     if (dtype == 0) return aligned ? launch_T<float, true>(a, st) : launch_T<float, false>(a, st);
     return aligned ? launch_T<uint16_t, true>(a, st) : launch_T<uint16_t, false>(a, st);
@@ -755,8 +705,11 @@ static hipError_t launch_any(int dtype, const VitArgs& a, hipStream_t st) {
 size_t viterbi_mid_doubles(int B, int C, int T) { return (size_t)B * C * 2 * T; }
 
 hipError_t launch_sequential_max(int dtype, const void* phi, const int32_t* lengths, int B, int N, int T,
-                                 uint8_t* bp, double* mid, float* best_score, int32_t* tags, hipStream_t st) {
-    return launch_any(dtype, VitArgs{phi, lengths, B, N, T, bp, mid, best_score, tags, 0, 1, nullptr, nullptr, nullptr}, st);
+                                 uint8_t* bp, double* mid, float* best_score, int32_t* tags, hipStream_t st, bool lanes,
+                                 int lane_poll_limit) {
+    if (lanes && !lane_max_supported(T)) return hipErrorInvalidValue;
+    return launch_any(dtype, VitArgs{phi, lengths, B, N, T, bp, mid, best_score, tags, 0, 1, nullptr, nullptr, nullptr}, st,
+                      lanes, lane_poll_limit);
 }
 
 template <typename G, bool ALIGNED>
@@ -786,13 +739,14 @@ hipError_t launch_structured_max(const float* emit, const float* trans, const in
 // Best path inside every chunk between the tags the max-plus scan has pinned at the chunk ends.
 hipError_t launch_chunked_max(int dtype, const void* phi, const int32_t* lengths, int B, int N, int T, uint8_t* bp,
                               double* mid, int32_t* tags, int chunk, const int32_t* pin, hipStream_t st,
-                              const float* emit, const float* trans) {
+                              const float* emit, const float* trans, bool lanes, int lane_poll_limit) {
     if (emit) {
         if (dtype != 0 || !trans || T > 128) return hipErrorInvalidValue;
         const VitArgs a{nullptr, lengths, B, N, T, bp, mid, nullptr, tags, chunk, (N + chunk - 1) / chunk, pin, emit, trans};
         return (T % 4) == 0 ? launch_structured_T<true>(a, st) : launch_structured_T<false>(a, st);
     }
-    return launch_any(dtype, VitArgs{phi, lengths, B, N, T, bp, mid, nullptr, tags, chunk, (N + chunk - 1) / chunk, pin, nullptr, nullptr}, st);
+    return launch_any(dtype, VitArgs{phi, lengths, B, N, T, bp, mid, nullptr, tags, chunk, (N + chunk - 1) / chunk, pin, nullptr, nullptr}, st,
+                      lanes && lane_max_supported(T), lane_poll_limit);
 }
 
 }  // namespace lccrf
