@@ -238,10 +238,25 @@ inline bool lanes_pay_sum(int op, int B, int N, int T) {
     return T <= 48 || op == 0;
 }
 
-// Whether the max-plus chains go to the chain-wave kernels (lccrf_lane_max.hip) under AUTO.
+// Whether LCCRF_ALGO_AUTO gives the max-plus chains to the chain-wave kernels (lccrf_lane_max.hip) rather than to
+// the one-wave / four-wave kernels.  They pay while every workgroup (two a sequence, eight waves each) is resident
+// at once: four a compute unit up to 16 tags, two up to 32, one up to 48 (their LDS rings).  Measured, whole
+// argmax, sequential / these (us): B=256 N=256 T=16 71 / 45, B=512 N=256 T=16 79 / 62, B=1024 N=64 T=16 33 / 38;
+// B=128 N=256 T=32 106 / 59, B=256 N=128 T=32 64 / 57, B=384 N=128 T=32 68 / 75; B=128 N=128 T=48 99 / 74,
+// B=64 N=256 T=40 181 / 117, B=256 N=128 T=48 127 / 130; above 48 tags the ring holds too few matrices
+// (B=32 N=256 T=64 182 / 208).
 inline bool lanes_pay_max(int B, int N, int T) {
-    (void)B; (void)N; (void)T;
-    return false;  // (until measured)
+    if (!lccrf::lane_max_supported(T) || T > 48 || N < 8) return false;
+    const int cus = current_device_cus();
+    return T <= 16 ? B <= 2 * cus : T <= 32 ? B <= cus : 2 * B <= cus;
+}
+// Whether AUTO takes the max-plus scan: where it would pay against the one-wave kernels, unless the chain-wave
+// kernels are quicker still (up to 16 tags they take about 18 us + 0.104 us a position whatever the batch, the
+// scan about 45 us + 0.9 ns a position of the batch: B=64 N=512 70 / 74, B=64 N=768 96 / 84, B=8 N=512 68 / 49,
+// B=128 N=512 70 / 97).
+inline bool scan_taken_max(int B, int N, int T) {
+    if (!scan_pays_max(B, N, T)) return false;
+    return !(lanes_pay_max(B, N, T) && (double)N * (0.104 - 0.0009 * B) < 27.0);
 }
 
 int sum_query(int op, const void* phi, int dt, const int32_t* lengths, int B, int N, int T, float* logZ,
@@ -326,7 +341,10 @@ int lccrf_auto_algo(lccrf_op op, int B, int N, int T) {
             break;
         case LCCRF_OP_LOG_PROB: scan = scan_pays_sum(B, N, T); break;
         case LCCRF_OP_SAMPLE: scan = scan_pays_sample(B, N, T); break;
-        case LCCRF_OP_ARGMAX: scan = scan_pays_max(B, N, T); break;
+        case LCCRF_OP_ARGMAX:
+            scan = scan_taken_max(B, N, T);
+            if (!scan && lanes_pay_max(B, N, T)) return LCCRF_ALGO_SEQUENTIAL_LANES;
+            break;
         case LCCRF_OP_ENTROPY:
         case LCCRF_OP_CROSS_ENTROPY: scan = scan_pays_entropy(B, N, T); break;
         default: return LCCRF_EINVAL;
@@ -372,7 +390,7 @@ int lccrf_argmax_algo(const void* phi, lccrf_dtype dt, const int32_t* lengths, i
     uint8_t* bp = reinterpret_cast<uint8_t*>(base + w.bp);
     double* mid = reinterpret_cast<double*>(base + w.mid);
     hipError_t e;
-    if (algo == LCCRF_ALGO_SCAN || (algo == LCCRF_ALGO_AUTO && scan_pays_max(B, N, T))) {
+    if (algo == LCCRF_ALGO_SCAN || (algo == LCCRF_ALGO_AUTO && scan_taken_max(B, N, T))) {
         int32_t* pin = reinterpret_cast<int32_t*>(base + w.pin);
         e = lccrf::launch_scan_pins(dt, phi, lengths, B, N, T, scan_chunk(B, N, T), reinterpret_cast<double*>(base + w.Mx),
                                     reinterpret_cast<uint8_t*>(base + w.K), pin,

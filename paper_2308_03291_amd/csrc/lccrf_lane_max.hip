@@ -57,7 +57,8 @@ struct MaxShape {
 template <int TP, int ROWS>
 struct MaxShared {
     using S = MaxShape<TP, ROWS>;
-    double M[S::RING][S::RPL / 2][64][2];  // M[slot][k / 2][lane][k % 2]: entry k of that lane (16-byte reads, lane after lane)
+    double M[S::RING][S::RPL / 2][65][2];  // M[slot][k / 2][lane][k % 2]: entry k of that lane (16-byte reads, lane after lane;
+                                           // 65: the helpers' scattered writes of one instruction spread over the banks)
     double V[kMaxVecRing][TP];             // V_q, the vector that enters step q, at [q % kMaxVecRing]
     double own[2][TP];                     // the vectors of a chain wave that goes on alone
     int ready[S::RING];                    // q + 1 once the matrix of step q sits in slot q % RING
@@ -327,7 +328,7 @@ __device__ __forceinline__ void max_helper_wave(const VitArgs& a, const VitSpan&
         const int s_ = (ok ? off : 0) / T, t0 = (ok ? off : 0) % T;
         const int yy = jb.dir == 0 ? s_ : t0, xx = jb.dir == 0 ? t0 : s_;
         const int k = yy % RPL;
-        lidx[m] = (((k >> 1) * 64 + (yy / RPL) * TP + xx) << 1) + (k & 1);
+        lidx[m] = (((k >> 1) * 65 + (yy / RPL) * TP + xx) << 1) + (k & 1);
     }
     float raw[2][NG][4];
     const auto load = [&](int j, int p) {
@@ -377,7 +378,7 @@ __device__ __forceinline__ void max_helper_wave(const VitArgs& a, const VitSpan&
                     d0.x = (double)raw[p][m][0]; d0.y = (double)raw[p][m][1];
                     d1.x = (double)raw[p][m][2]; d1.y = (double)raw[p][m][3];
                     *reinterpret_cast<double2*>(Ms + lidx[m]) = d0;
-                    *reinterpret_cast<double2*>(Ms + lidx[m] + 128) = d1;
+                    *reinterpret_cast<double2*>(Ms + lidx[m] + 130) = d1;
                 }
             }
         if (lane == 0) lds_store_release(&sh.ready[slot], q + 1);
@@ -443,7 +444,7 @@ __global__ __launch_bounds__(64 * kMaxWaves) void viterbi_lane_kernel(VitArgs a,
     if (tid == 0) { sh.done = 0; sh.stop = 0x7fffffff; }
     if (T != TP) {  // entries past the tag set: the helpers never write them
         double* Mz = &sh.M[0][0][0][0];
-        for (int k = tid; k < S::RING * S::RPL * 64; k += 64 * kMaxWaves) Mz[k] = -__builtin_huge_val();
+        for (int k = tid; k < S::RING * S::RPL * 65; k += 64 * kMaxWaves) Mz[k] = -__builtin_huge_val();
     }
     __syncthreads();
     if (wv == 0) {
@@ -455,7 +456,7 @@ __global__ __launch_bounds__(64 * kMaxWaves) void viterbi_lane_kernel(VitArgs a,
 }
 
 // ---------------------------------------------------------------------------------------
-// Plain potentials, whole sequences or the chunks of the max-plus scan, up to 64 tags.
+// Plain potentials, whole sequences, 4 .. 64 tags in multiples of four.
 bool lane_max_supported(int T) { return T >= 4 && T <= 64 && T % 4 == 0; }  // (16-byte pieces of a row)
 
 template <int TP, int ROWS, typename TIN>
@@ -476,7 +477,7 @@ static hipError_t launch_max_T(const VitArgs& a, int poll_limit, hipStream_t st)
 }
 
 hipError_t launch_lane_max_chains(int dtype, const VitArgs& a, int poll_limit, hipStream_t st) {
-    if (!lane_max_supported(a.T) || a.emit) return hipErrorInvalidValue;
+    if (!lane_max_supported(a.T) || a.emit || a.chunk > 0) return hipErrorInvalidValue;
     return dtype == 0 ? launch_max_T<float>(a, poll_limit, st) : launch_max_T<uint16_t>(a, poll_limit, st);
 }
 

@@ -126,8 +126,7 @@ hipError_t launch_scan_pins(int dtype, const void* phi, const int32_t* lengths, 
 // mid: viterbi_mid_doubles(B, C, T) doubles of scratch.
 hipError_t launch_chunked_max(int dtype, const void* phi, const int32_t* lengths, int B, int N, int T, uint8_t* bp,
                               double* mid, int32_t* tags, int chunk, const int32_t* pin, hipStream_t st,
-                              const float* emit = nullptr, const float* trans = nullptr, bool lanes = false,
-                              int lane_poll_limit = 1 << 16);
+                              const float* emit = nullptr, const float* trans = nullptr);
 
 // Entropy H(p) [B] in one read of phi (lccrf_extras.hip, one-wave kernels for T <= 32).  ua / ub / Oa / Ob
 // as for launch_sequential_sum (only the rows of the meeting positions are written); ha, hb: [B][T] floats.

@@ -739,14 +739,13 @@ hipError_t launch_structured_max(const float* emit, const float* trans, const in
 // Best path inside every chunk between the tags the max-plus scan has pinned at the chunk ends.
 hipError_t launch_chunked_max(int dtype, const void* phi, const int32_t* lengths, int B, int N, int T, uint8_t* bp,
                               double* mid, int32_t* tags, int chunk, const int32_t* pin, hipStream_t st,
-                              const float* emit, const float* trans, bool lanes, int lane_poll_limit) {
+                              const float* emit, const float* trans) {
     if (emit) {
         if (dtype != 0 || !trans || T > 128) return hipErrorInvalidValue;
         const VitArgs a{nullptr, lengths, B, N, T, bp, mid, nullptr, tags, chunk, (N + chunk - 1) / chunk, pin, emit, trans};
         return (T % 4) == 0 ? launch_structured_T<true>(a, st) : launch_structured_T<false>(a, st);
     }
-    return launch_any(dtype, VitArgs{phi, lengths, B, N, T, bp, mid, nullptr, tags, chunk, (N + chunk - 1) / chunk, pin, nullptr, nullptr}, st,
-                      lanes && lane_max_supported(T), lane_poll_limit);
+    return launch_any(dtype, VitArgs{phi, lengths, B, N, T, bp, mid, nullptr, tags, chunk, (N + chunk - 1) / chunk, pin, nullptr, nullptr}, st);
 }
 
 }  // namespace lccrf

@@ -59,7 +59,9 @@ def test_workspace_sizes(lib):
 
 
 def test_auto_schedule_is_reported_without_a_gpu(lib):
-    """lccrf_auto_algo is host arithmetic: long chains over few tags in small batches take the scan."""
+    """lccrf_auto_algo is host arithmetic: long chains over few tags in small batches take the scan.  (Without a
+    device there are no compute units to count and the chain-wave kernels are never chosen; their share of AUTO
+    is asserted on the GPU.)"""
     assert binding.auto_algo(binding.OP_MARGINALS, 4, 16384, 16) == binding.ALGO_SCAN       # config 5
     assert binding.auto_algo(binding.OP_ARGMAX, 4, 16384, 16) == binding.ALGO_SCAN
     assert binding.auto_algo(binding.OP_MARGINALS, 64, 512, 128) == binding.ALGO_SEQUENTIAL  # config 4

@@ -121,3 +121,20 @@ def test_lane_max_paper_shape(crf):
     w = workloads.WORKLOADS["paper_lccrf"]
     phi = workloads.phi_batch(w)
     same_as_sequential(crf, phi, None, "lane max paper shape")
+
+
+def test_auto_takes_the_chain_wave_kernels_where_they_pay(crf):
+    """lccrf_auto_algo for the argmax on a 256-unit device: batches whose workgroups are all resident at once, up to
+    48 tags in multiples of four; the max-plus scan only where it is quicker still."""
+    A = lambda B, N, T: crf.auto_algo(crf.OP_ARGMAX, B, N, T)
+    assert A(128, 256, 32) == crf.ALGO_SEQUENTIAL_LANES     # the paper's shape
+    assert A(32, 64, 32) == crf.ALGO_SEQUENTIAL_LANES       # config 2
+    assert A(128, 128, 48) == crf.ALGO_SEQUENTIAL_LANES     # config 3
+    assert A(256, 256, 16) == crf.ALGO_SEQUENTIAL_LANES
+    assert A(64, 512, 16) == crf.ALGO_SEQUENTIAL_LANES      # quicker than the scan there
+    assert A(64, 1024, 16) == crf.ALGO_SCAN
+    assert A(4, 16384, 16) == crf.ALGO_SCAN                 # config 5
+    assert A(1024, 64, 32) == crf.ALGO_SEQUENTIAL           # too many sequences at once
+    assert A(32, 256, 64) == crf.ALGO_SEQUENTIAL            # more than 48 tags
+    assert A(32, 64, 30) == crf.ALGO_SEQUENTIAL             # not a multiple of four
+    assert A(4, 8, 5) == crf.ALGO_SEQUENTIAL                # config 1

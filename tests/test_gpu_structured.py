@@ -122,7 +122,8 @@ def test_structured_under_the_scan(crf, oracle_mod, chunk, T, N, k):
     lens = _scan_lens(N, k or 8)
     B = len(lens)
     assert crf.auto_algo(crf.OP_MARGINALS, B, N, T) == crf.ALGO_SCAN
-    assert crf.auto_algo(crf.OP_ARGMAX, B, N, T) == (crf.ALGO_SCAN if T <= 16 and N >= 16 * (k or 8) else crf.ALGO_SEQUENTIAL)
+    dense_chains = crf.ALGO_SEQUENTIAL_LANES if T % 4 == 0 and T <= 48 else crf.ALGO_SEQUENTIAL  # (the dense call's own choice)
+    assert crf.auto_algo(crf.OP_ARGMAX, B, N, T) == (crf.ALGO_SCAN if T <= 16 and N >= 16 * (k or 8) else dense_chains)
     emit, trans = _make(7400 + 13 * T + N + k, B, N, T)
     _check(crf, oracle_mod, emit, trans, lens, f"structured scan T={T} N={N} k={k}")
 
