@@ -193,7 +193,8 @@ def bench_config(crf, workloads, oracle, torch, timer, key, calls, dev, with_par
         taken = crf.auto_algo(op, w.B, w.N, w.T)
         scan = taken == crf.ALGO_SCAN
         scan_any = scan_any or (scan and name == "marginals")
-        q = {"schedule": "scan" if scan else "sequential (chain wave + producer waves)" if taken == crf.ALGO_SEQUENTIAL_LANES
+        lanes_label = "sequential (chain wave + helper waves)" if name == "argmax" else "sequential (chain wave + producer waves)"
+        q = {"schedule": "scan" if scan else lanes_label if taken == crf.ALGO_SEQUENTIAL_LANES
              else "sequential", "algorithmic_bytes": eff_pots * bpp,
              "warm": timer.run(fn, calls, cold=False)}
         states = ["warm"]

@@ -50,10 +50,11 @@
  *    lccrf_set_pair_poll_limit); a pair that gives its sequence up hands it to the
  *    one-workgroup kernel, which rounds differently, so where that hand-over depends
  *    on timing two runs may differ in the low-order bits (far inside the tolerance).
- *    LCCRF_ALGO_SEQUENTIAL never uses pairs.  Likewise a chain of LCCRF_ALGO_SEQUENTIAL_LANES (which AUTO
- *    takes for mid-sized batches of 17 .. 64 tags) whose producers fall behind its poll limit
+ *    LCCRF_ALGO_SEQUENTIAL never uses pairs.  Likewise a sum-product chain of LCCRF_ALGO_SEQUENTIAL_LANES
+ *    (which AUTO takes for mid-sized batches of 17 .. 64 tags) whose producers fall behind its poll limit
  *    (lccrf_set_lane_poll_limit; milliseconds, not seen in practice) finishes in the log domain and
- *    rounds differently from a run in which they kept up.
+ *    rounds differently from a run in which they kept up.  (lccrf_argmax is bit-identical from run to run
+ *    under every schedule: a max-plus chain that stops waiting computes the same sums and maxima alone.)
  */
 #ifndef LCCRF_H
 #define LCCRF_H
@@ -99,7 +100,11 @@ typedef enum {
                                   other waves of its workgroup stream and exponentiate the potentials and
                                   write the marginals; positions whose sums leave the range of single
                                   precision (or hold -inf) are taken in the log domain.  lccrf_log_partition
-                                  and lccrf_marginals only, 8 <= T <= 64 with T a multiple of 4, else
+                                  and lccrf_marginals at 8 <= T <= 64 with T a multiple of 4.  For
+                                  lccrf_argmax (4 <= T <= 64, T a multiple of 4) the same split in the max-plus
+                                  semiring: one wave runs the scores in double precision, the others stream
+                                  the potentials and find the pointers; tags and scores are those of
+                                  LCCRF_ALGO_SEQUENTIAL bit for bit.  Other queries and tag counts:
                                   LCCRF_ENOTIMPL; AUTO takes it where the batch leaves the chip latency-bound */
 } lccrf_algo;
 
@@ -329,7 +334,8 @@ int lccrf_set_pair_poll_limit(int polls);
  * depend on the limit beyond rounding.  A process-wide tuning knob.  Default 65536 looks (a few milliseconds at
  * worst; a matrix is normally there before it is asked for), -1 restores it, 0 gives up at the first look that
  * fails (nearly every chain then runs in the log domain from its first position: for tests of that path), more
- * than 2^24 returns LCCRF_EINVAL. */
+ * than 2^24 returns LCCRF_EINVAL.  The chain wave of lccrf_argmax under the same schedule waits for its helper
+ * waves by the same limit, and then goes on alone with the same arithmetic: identical tags and scores. */
 int lccrf_set_lane_poll_limit(int polls);
 
 /* The schedule LCCRF_ALGO_AUTO takes for `op` at this shape under the current chunk size:
