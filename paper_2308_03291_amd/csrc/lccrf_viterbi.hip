@@ -23,7 +23,7 @@
 
 namespace lccrf {
 
-constexpr int kTraceBytes = 16384;  // LDS window of pointers walked by each trace
+constexpr int kTraceBytes = 8192;  // LDS window of pointers walked by each direction of a trace
 
 // Forward chains at 64 < T <= 128 (T % 4 == 0) turn their tiles through LDS like the sum-product
 // first pass does (lccrf_chain.hip): a wave then owns 8 complete columns and the maximum over
@@ -574,14 +574,27 @@ __global__ __launch_bounds__(64) void viterbi_wave_kernel(VitArgs a) {
 }
 
 // Joins the two chains at the meeting point and reads off the path.
-__global__ __launch_bounds__(128) void viterbi_trace_kernel(VitArgs a) {
-    __shared__ uint8_t window[2][kTraceBytes];
+//
+// Following the pointers is a chain of dependent LDS reads, one per position (about a hundred cycles each).  It is
+// cut by walking stretches of the path before their entry tag is known: a half of the workgroup serves a
+// direction, its threads (stretch g, tag t) follow the pointers of stretch g from EVERY entry tag t and record
+// the tags they pass; one thread then links the stretches (the tag a stretch is left on, given the tag it was
+// entered on, enters the next), and all threads copy the recorded tags of the stretches' true entry tags out.
+// The dependent chain is R / G + G lookups instead of R for R positions in G = threads / T stretches.
+constexpr int kTraceThreads = 512;             // half of them per direction
+constexpr int kTraceHalf = kTraceThreads / 2;
+__global__ __launch_bounds__(kTraceThreads) void viterbi_trace_kernel(VitArgs a) {
+    __shared__ __attribute__((aligned(16))) uint8_t window[2][kTraceBytes];  // pointers of the rows being walked
+    __shared__ uint8_t passed[2][kTraceBytes + kTraceHalf];  // [step][stretch][entry tag]: the tag reached after that step
+    __shared__ uint8_t left_on[2][kTraceHalf];  // [stretch][entry tag]: the tag the stretch is left on
+    __shared__ int entered[2][kTraceHalf + 1];  // the tag every stretch is entered on
     __shared__ int start;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int dir = tid / kTraceHalf, me = tid % kTraceHalf;  // dir 0 walks down, 1 up
     const VitSpan sp = vit_span(a, blockIdx.x);
     const int b = sp.b, N = a.N, T = a.T, L = sp.L;
     int32_t* tags = a.tags + (size_t)b * N;
-    for (int i = (L > sp.t0 ? L : sp.t0) + tid; i < sp.t1; i += 128) tags[i] = -1;
+    for (int i = (L > sp.t0 ? L : sp.t0) + tid; i < sp.t1; i += kTraceThreads) tags[i] = -1;
     if (L == 0) {
         if (a.chunk <= 0 && tid == 0 && a.best_score) a.best_score[b] = 0.f;
         return;
@@ -592,7 +605,7 @@ __global__ __launch_bounds__(128) void viterbi_trace_kernel(VitArgs a) {
     const double* mid = a.mid + ((size_t)b * a.C + sp.c) * 2 * T;
     const double ninf = -__builtin_huge_val();
 
-    if (wave == 0) {  // best tag at the meeting point: first maximum of delta_h + eps_h
+    if (tid < 64) {  // best tag at the meeting point: first maximum of delta_h + eps_h
         double bv = ninf;
         int ba = kNoArg;
         for (int t = lane; t < T; t += 64) {
@@ -612,37 +625,64 @@ __global__ __launch_bounds__(128) void viterbi_trace_kernel(VitArgs a) {
     }
     __syncthreads();
     const int rows_per_window = kTraceBytes / T;
-    int y = start;
+    const int G = kTraceHalf / T;   // stretches walked at once (T <= 256: at least one)
+    const int g = me / T, t = me % T;
+    int y = start;                  // the tag the next window is entered on (the same in every thread of a direction)
     if (tid == 0) tags[h] = y;
-    // wave 0 walks down: row r yields the tag of position r - 1 (a chunk leaves the tag of its entry
-    // position p0 to the chunk that ends there); wave 1 walks up: row r yields the tag of position r
+    // downwards row r yields the tag of position r - 1 (a chunk leaves the tag of its entry position p0 to the
+    // chunk that ends there); upwards row r yields the tag of position r
     const int stop = sp.t0 == 0 ? 1 : sp.t0 + 1;
     int hi = h + 1;   // rows [stop, hi) still to walk down
     int lo = h + 1;   // rows [lo, e] still to walk up
-    while (hi > stop || lo <= e) {  // both waves make the same number of trips: barriers stay matched
+    while (hi > stop || lo <= e) {  // both directions make the same number of trips: barriers stay matched
         const int dlo = (hi - rows_per_window > stop) ? hi - rows_per_window : stop;
         const int uhi = (lo + rows_per_window - 1 < e) ? lo + rows_per_window - 1 : e;
-        if (wave == 0) {
-            const int nbytes = hi > stop ? (hi - dlo) * T : 0;
-            const uint8_t* src = bpb + (size_t)dlo * T;
-            for (int k = lane; k < nbytes; k += 64) window[0][k] = src[k];
-        } else {
-            const int nbytes = lo <= e ? (uhi - lo + 1) * T : 0;
-            const uint8_t* src = bpb + (size_t)lo * T;
-            for (int k = lane; k < nbytes; k += 64) window[1][k] = src[k];
+        // rows of this trip: first row in memory, their number, and whether they are walked from the last one down
+        const int first = dir == 0 ? dlo : lo;
+        const int R = dir == 0 ? (hi > stop ? hi - dlo : 0) : (lo <= e ? uhi - lo + 1 : 0);
+        {
+            const int nbytes = R * T;
+            const uint8_t* src = bpb + (size_t)first * T;
+            int k0 = 0;
+            if ((reinterpret_cast<uintptr_t>(src) & 15) == 0) {
+                const int n16 = nbytes / 16;
+                const uint4* s16 = reinterpret_cast<const uint4*>(src);
+                uint4* d16 = reinterpret_cast<uint4*>(window[dir]);
+                for (int k = me; k < n16; k += kTraceHalf) d16[k] = s16[k];
+                k0 = n16 * 16;
+            }
+            for (int k = k0 + me; k < nbytes; k += kTraceHalf) window[dir][k] = src[k];
         }
         __syncthreads();
-        if (tid == 0 && hi > stop) {
-            for (int r = hi - 1; r >= dlo; --r) {
-                y = window[0][(r - dlo) * T + y];
-                tags[r - 1] = y;
+        const int S = (R + G - 1) / G;  // rows a stretch
+        if (g < G && R > 0) {
+            int yy = t;
+            for (int j = 0; j < S; ++j) {
+                const int k = g * S + j;  // the k-th row walked on this trip
+                if (k >= R) break;
+                yy = window[dir][(dir == 0 ? R - 1 - k : k) * T + yy];
+                passed[dir][(j * G + g) * T + t] = (uint8_t)yy;
             }
+            left_on[dir][g * T + t] = (uint8_t)yy;
         }
-        if (tid == 64 && lo <= e) {
-            for (int r = lo; r <= uhi; ++r) {
-                y = window[1][(r - lo) * T + y];
-                tags[r] = y;
+        __syncthreads();
+        if (me == 0 && R > 0) {
+            int yy = y;
+            for (int q = 0; q < G; ++q) {
+                entered[dir][q] = yy;
+                yy = left_on[dir][q * T + yy];
             }
+            entered[dir][G] = yy;
+        }
+        __syncthreads();
+        if (R > 0) {
+            for (int k = me; k < R; k += kTraceHalf) {
+                const int q = k / S, j = k % S;
+                const int tag = passed[dir][(j * G + q) * T + entered[dir][q]];
+                if (dir == 0) tags[first + R - 1 - k - 1] = tag;
+                else tags[first + k] = tag;
+            }
+            y = entered[dir][G];
         }
         __syncthreads();
         if (hi > stop) hi = dlo;
@@ -663,7 +703,7 @@ static hipError_t launch_geo(const VitArgs& a, hipStream_t st) {
     hipLaunchKernelGGL((viterbi_half_kernel<G, TIN, ALIGNED>), dim3(2 * a.B * a.C), dim3(G::W), turn_bytes, st, a);
     e = hipGetLastError();
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(viterbi_trace_kernel, dim3(a.B * a.C), dim3(128), 0, st, a);
+    hipLaunchKernelGGL(viterbi_trace_kernel, dim3(a.B * a.C), dim3(kTraceThreads), 0, st, a);
     return hipGetLastError();
 }
 
@@ -672,7 +712,7 @@ static hipError_t launch_wave_vit(const VitArgs& a, hipStream_t st) {
     hipLaunchKernelGGL((viterbi_wave_kernel<TP, TIN, ALIGNED, STRUCT>), dim3(2 * a.B * a.C), dim3(64), 0, st, a);
     const hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(viterbi_trace_kernel, dim3(a.B * a.C), dim3(128), 0, st, a);
+    hipLaunchKernelGGL(viterbi_trace_kernel, dim3(a.B * a.C), dim3(kTraceThreads), 0, st, a);
     return hipGetLastError();
 }
 
@@ -686,7 +726,7 @@ static hipError_t launch_T(const VitArgs& a, hipStream_t st) {
     hipLaunchKernelGGL((viterbi_stream_kernel<TIN, ALIGNED>), dim3(2 * a.B * a.C), dim3(1024), 0, st, a);
     const hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(viterbi_trace_kernel, dim3(a.B * a.C), dim3(128), 0, st, a);
+    hipLaunchKernelGGL(viterbi_trace_kernel, dim3(a.B * a.C), dim3(kTraceThreads), 0, st, a);
     return hipGetLastError();
 }
 
@@ -694,7 +734,7 @@ static hipError_t launch_any(int dtype, const VitArgs& a, hipStream_t st, bool l
     if (lanes) {
         const hipError_t e = launch_lane_max_chains(dtype, a, lane_poll_limit, st);
         if (e != hipSuccess) return e;
-        hipLaunchKernelGGL(viterbi_trace_kernel, dim3(a.B * a.C), dim3(128), 0, st, a);
+        hipLaunchKernelGGL(viterbi_trace_kernel, dim3(a.B * a.C), dim3(kTraceThreads), 0, st, a);
         return hipGetLastError();
     }
     const bool aligned = (a.T % 4) == 0;
@@ -717,7 +757,7 @@ static hipError_t launch_structured_geo(const VitArgs& a, hipStream_t st) {
     hipLaunchKernelGGL((viterbi_half_kernel<G, float, ALIGNED, true>), dim3(2 * a.B * a.C), dim3(G::W), 0, st, a);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(viterbi_trace_kernel, dim3(a.B * a.C), dim3(128), 0, st, a);
+    hipLaunchKernelGGL(viterbi_trace_kernel, dim3(a.B * a.C), dim3(kTraceThreads), 0, st, a);
     return hipGetLastError();
 }
 template <bool ALIGNED>
