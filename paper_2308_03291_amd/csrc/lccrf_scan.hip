@@ -908,10 +908,18 @@ __device__ __forceinline__ void maxplus_product(int first, int last, int T, doub
 #pragma unroll
         for (int jj = 0; jj < 4; ++jj) X[r][4 * q + jj] = get(ring[slot], jj);
         __syncthreads();
+        // all sixteen rows of this lane's four columns first (left to itself the compiler waits for every LDS
+        // read before it issues the next: sixteen to thirty-two latencies a position), then the arithmetic
+        XT xr[16][4];
+#pragma unroll
+        for (int s = 0; s < 16; ++s)
+#pragma unroll
+            for (int jj = 0; jj < 4; ++jj) xr[s][jj] = X[s][4 * q + jj];
+        __builtin_amdgcn_sched_barrier(0);
         double best[4] = {ninf, ninf, ninf, ninf};
         const auto row = [&](int s, double m) {
 #pragma unroll
-            for (int jj = 0; jj < 4; ++jj) best[jj] = fmax(best[jj], m + (double)X[s][4 * q + jj]);
+            for (int jj = 0; jj < 4; ++jj) best[jj] = fmax(best[jj], m + (double)xr[s][jj]);
         };
 #pragma unroll
         for (int jj = 0; jj < 4; ++jj) {
@@ -932,7 +940,7 @@ struct MaxSlotD { double x[4]; };
 
 template <typename TIN, bool STRUCT = false>
 __global__ __launch_bounds__(64) void chunk_maxplus_kernel(MaxScanArgs a) {
-    __shared__ __attribute__((aligned(16))) float Xs[2][16][16];
+    __shared__ __attribute__((aligned(16))) double Xs[2][16][16];
     const int lane = threadIdx.x, r = lane >> 2, q = lane & 3;
     const int b = blockIdx.x / a.C, c = blockIdx.x % a.C;
     const int T = a.T, N = a.N;
@@ -959,25 +967,25 @@ __global__ __launch_bounds__(64) void chunk_maxplus_kernel(MaxScanArgs a) {
             tr[jj] = a.trans[off[jj]];
             col[jj] = 4 * q + jj < T ? 4 * q + jj : T - 1;
         }
-        maxplus_product<kScanPF, MaxSlotF, float>(
+        maxplus_product<kScanPF, MaxSlotF, double>(
             first, last, T, a.Mx + ((size_t)b * a.C + c) * 256,
             [&](int i, MaxSlotF& sl) {
                 const float* m = emb + (size_t)i * T;
 #pragma unroll
                 for (int jj = 0; jj < 4; ++jj) sl.x[jj] = m[col[jj]];
             },
-            [&](const MaxSlotF& sl, int jj) { return in[jj] ? tr[jj] + sl.x[jj] : LCCRF_NEG_INF; }, Xs);
+            [&](const MaxSlotF& sl, int jj) { return (double)(in[jj] ? tr[jj] + sl.x[jj] : LCCRF_NEG_INF); }, Xs);
         return;
     }
     const TIN* phib = static_cast<const TIN*>(a.phi) + (size_t)b * N * TT;
-    maxplus_product<kScanPF, MaxSlotF, float>(
+    maxplus_product<kScanPF, MaxSlotF, double>(
         first, last, T, a.Mx + ((size_t)b * a.C + c) * 256,
         [&](int i, MaxSlotF& sl) {
             const TIN* m = phib + (size_t)i * TT;
 #pragma unroll
             for (int jj = 0; jj < 4; ++jj) sl.x[jj] = Elem<TIN>::get(m + off[jj]);
         },
-        [&](const MaxSlotF& sl, int jj) { return in[jj] ? sl.x[jj] : LCCRF_NEG_INF; }, Xs);
+        [&](const MaxSlotF& sl, int jj) { return (double)(in[jj] ? sl.x[jj] : LCCRF_NEG_INF); }, Xs);
 }
 
 // One wave per group of GS chunks: the max-plus product of the group's chunk matrices.
