@@ -437,14 +437,18 @@ __global__ __launch_bounds__(1024) void viterbi_stream_kernel(VitArgs a) {
 //   backward: LPC lanes share a row s (lane = s LPC + part), each takes RPL consecutive columns
 //             (vector loads), merged in the same way.
 // Same outputs as viterbi_half_kernel: pointers in bp, the two vectors of the meeting point in mid.
-template <int TP, typename TIN, bool ALIGNED, bool STRUCT>
-__global__ __launch_bounds__(64) void viterbi_wave_kernel(VitArgs a) {
+// ALONE: the wave is the whole workgroup (its barrier is a wait for its own LDS writes).  Otherwise it shares a
+// workgroup with waves that make a different number of steps, and must not meet them at a barrier: LDS executes a
+// wave's instructions in order, so the wave's own writes are there for its later reads, and the compiler only has
+// to keep the order.
+template <bool ALONE>
+__device__ __forceinline__ void wave_step_end() {
+    if constexpr (ALONE) __syncthreads();
+    else __atomic_signal_fence(__ATOMIC_SEQ_CST);
+}
+template <int TP, typename TIN, bool ALIGNED, bool STRUCT, bool ALONE>
+__device__ __forceinline__ void viterbi_wave_chain(const VitArgs& a, const VitSpan& sp, int dir, int lane, double (*dvec)[TP]) {
     constexpr int LPC = 64 / TP, RPL = TP / LPC, PF = 3;
-    __shared__ double dvec[2][TP];
-    const int lane = threadIdx.x;
-    const int dir = blockIdx.x & 1;
-    const VitSpan sp = vit_span(a, blockIdx.x >> 1);
-    if (sp.empty) return;
     const int b = sp.b, N = a.N, T = a.T;
     const int p0 = sp.p0, e = sp.e, h = meeting_point(p0, e);
     const size_t TT = (size_t)T * T;
@@ -467,7 +471,7 @@ __global__ __launch_bounds__(64) void viterbi_wave_kernel(VitArgs a) {
         }
         dvec[0][lane] = v0;
     }
-    __syncthreads();
+    wave_step_end<ALONE>();
     int buf = 0;
     float ring[PF][RPL];
 
@@ -512,7 +516,7 @@ __global__ __launch_bounds__(64) void viterbi_wave_kernel(VitArgs a) {
                 dvec[buf ^ 1][t] = bv;
                 if (t < T) bpb[(size_t)i * T + t] = (uint8_t)(ba == kNoArg ? 0 : ba);
             }
-            __syncthreads();
+            wave_step_end<ALONE>();
             buf ^= 1;
         });
     } else {
@@ -566,11 +570,19 @@ __global__ __launch_bounds__(64) void viterbi_wave_kernel(VitArgs a) {
                 dvec[buf ^ 1][s] = bv;
                 if (s < T) bpb[(size_t)i * T + s] = (uint8_t)(ba == kNoArg ? 0 : ba);
             }
-            __syncthreads();
+            wave_step_end<ALONE>();
             buf ^= 1;
         });
     }
     if (lane < T) mid[lane] = dvec[buf][lane];
+}
+
+template <int TP, typename TIN, bool ALIGNED, bool STRUCT>
+__global__ __launch_bounds__(64) void viterbi_wave_kernel(VitArgs a) {
+    __shared__ double dvec[2][TP];
+    const VitSpan sp = vit_span(a, blockIdx.x >> 1);
+    if (sp.empty) return;
+    viterbi_wave_chain<TP, TIN, ALIGNED, STRUCT, true>(a, sp, blockIdx.x & 1, threadIdx.x, dvec);
 }
 
 // Joins the two chains at the meeting point and reads off the path.
@@ -582,19 +594,24 @@ __global__ __launch_bounds__(64) void viterbi_wave_kernel(VitArgs a) {
 // entered on, enters the next), and all threads copy the recorded tags of the stretches' true entry tags out.
 // The dependent chain is R / G + G lookups instead of R for R positions in G = threads / T stretches.
 constexpr int kTraceThreads = 512;             // half of them per direction
-constexpr int kTraceHalf = kTraceThreads / 2;
-__global__ __launch_bounds__(kTraceThreads) void viterbi_trace_kernel(VitArgs a) {
-    __shared__ __attribute__((aligned(16))) uint8_t window[2][kTraceBytes];  // pointers of the rows being walked
-    __shared__ uint8_t passed[2][kTraceBytes + kTraceHalf];  // [step][stretch][entry tag]: the tag reached after that step
-    __shared__ uint8_t left_on[2][kTraceHalf];  // [stretch][entry tag]: the tag the stretch is left on
-    __shared__ int entered[2][kTraceHalf + 1];  // the tag every stretch is entered on
-    __shared__ int start;
+template <int THREADS, int BYTES>
+struct TraceShared {
+    static constexpr int HALF = THREADS / 2;
+    __attribute__((aligned(16))) uint8_t window[2][BYTES];  // pointers of the rows being walked
+    uint8_t passed[2][BYTES + HALF];  // [step][stretch][entry tag]: the tag reached after that step
+    uint8_t left_on[2][HALF];         // [stretch][entry tag]: the tag the stretch is left on
+    int entered[2][HALF + 1];         // the tag every stretch is entered on
+    int start;
+};
+// By all THREADS threads of a workgroup (every one of them must call it: it holds barriers).
+template <int THREADS, int BYTES>
+__device__ __forceinline__ void trace_span(const VitArgs& a, const VitSpan& sp, TraceShared<THREADS, BYTES>& sm) {
+    constexpr int kHalf = THREADS / 2;
     const int tid = threadIdx.x, lane = tid & 63;
-    const int dir = tid / kTraceHalf, me = tid % kTraceHalf;  // dir 0 walks down, 1 up
-    const VitSpan sp = vit_span(a, blockIdx.x);
+    const int dir = tid / kHalf, me = tid % kHalf;  // dir 0 walks down, 1 up
     const int b = sp.b, N = a.N, T = a.T, L = sp.L;
     int32_t* tags = a.tags + (size_t)b * N;
-    for (int i = (L > sp.t0 ? L : sp.t0) + tid; i < sp.t1; i += kTraceThreads) tags[i] = -1;
+    for (int i = (L > sp.t0 ? L : sp.t0) + tid; i < sp.t1; i += THREADS) tags[i] = -1;
     if (L == 0) {
         if (a.chunk <= 0 && tid == 0 && a.best_score) a.best_score[b] = 0.f;
         return;
@@ -619,15 +636,15 @@ __global__ __launch_bounds__(kTraceThreads) void viterbi_trace_kernel(VitArgs a)
             take_better(bv, ba, pv, pa);
         }
         if (lane == 0) {
-            start = (ba == kNoArg) ? 0 : ba;
+            sm.start = (ba == kNoArg) ? 0 : ba;
             if (a.chunk <= 0 && a.best_score) a.best_score[b] = (float)bv;
         }
     }
     __syncthreads();
-    const int rows_per_window = kTraceBytes / T;
-    const int G = kTraceHalf / T;   // stretches walked at once (T <= 256: at least one)
+    const int rows_per_window = BYTES / T;
+    const int G = kHalf / T > 0 ? kHalf / T : 1;   // stretches walked at once
     const int g = me / T, t = me % T;
-    int y = start;                  // the tag the next window is entered on (the same in every thread of a direction)
+    int y = sm.start;               // the tag the next window is entered on (the same in every thread of a direction)
     if (tid == 0) tags[h] = y;
     // downwards row r yields the tag of position r - 1 (a chunk leaves the tag of its entry position p0 to the
     // chunk that ends there); upwards row r yields the tag of position r
@@ -637,7 +654,7 @@ __global__ __launch_bounds__(kTraceThreads) void viterbi_trace_kernel(VitArgs a)
     while (hi > stop || lo <= e) {  // both directions make the same number of trips: barriers stay matched
         const int dlo = (hi - rows_per_window > stop) ? hi - rows_per_window : stop;
         const int uhi = (lo + rows_per_window - 1 < e) ? lo + rows_per_window - 1 : e;
-        // rows of this trip: first row in memory, their number, and whether they are walked from the last one down
+        // rows of this trip: the first of them in memory and their number
         const int first = dir == 0 ? dlo : lo;
         const int R = dir == 0 ? (hi > stop ? hi - dlo : 0) : (lo <= e ? uhi - lo + 1 : 0);
         {
@@ -647,47 +664,69 @@ __global__ __launch_bounds__(kTraceThreads) void viterbi_trace_kernel(VitArgs a)
             if ((reinterpret_cast<uintptr_t>(src) & 15) == 0) {
                 const int n16 = nbytes / 16;
                 const uint4* s16 = reinterpret_cast<const uint4*>(src);
-                uint4* d16 = reinterpret_cast<uint4*>(window[dir]);
-                for (int k = me; k < n16; k += kTraceHalf) d16[k] = s16[k];
+                uint4* d16 = reinterpret_cast<uint4*>(sm.window[dir]);
+                for (int k = me; k < n16; k += kHalf) d16[k] = s16[k];
                 k0 = n16 * 16;
             }
-            for (int k = k0 + me; k < nbytes; k += kTraceHalf) window[dir][k] = src[k];
+            for (int k = k0 + me; k < nbytes; k += kHalf) sm.window[dir][k] = src[k];
         }
         __syncthreads();
         const int S = (R + G - 1) / G;  // rows a stretch
-        if (g < G && R > 0) {
+        if (g < G && t < T && R > 0) {
             int yy = t;
             for (int j = 0; j < S; ++j) {
                 const int k = g * S + j;  // the k-th row walked on this trip
                 if (k >= R) break;
-                yy = window[dir][(dir == 0 ? R - 1 - k : k) * T + yy];
-                passed[dir][(j * G + g) * T + t] = (uint8_t)yy;
+                yy = sm.window[dir][(dir == 0 ? R - 1 - k : k) * T + yy];
+                sm.passed[dir][(j * G + g) * T + t] = (uint8_t)yy;
             }
-            left_on[dir][g * T + t] = (uint8_t)yy;
+            sm.left_on[dir][g * T + t] = (uint8_t)yy;
         }
         __syncthreads();
         if (me == 0 && R > 0) {
             int yy = y;
             for (int q = 0; q < G; ++q) {
-                entered[dir][q] = yy;
-                yy = left_on[dir][q * T + yy];
+                sm.entered[dir][q] = yy;
+                yy = sm.left_on[dir][q * T + yy];
             }
-            entered[dir][G] = yy;
+            sm.entered[dir][G] = yy;
         }
         __syncthreads();
         if (R > 0) {
-            for (int k = me; k < R; k += kTraceHalf) {
+            for (int k = me; k < R; k += kHalf) {
                 const int q = k / S, j = k % S;
-                const int tag = passed[dir][(j * G + q) * T + entered[dir][q]];
+                const int tag = sm.passed[dir][(j * G + q) * T + sm.entered[dir][q]];
                 if (dir == 0) tags[first + R - 1 - k - 1] = tag;
                 else tags[first + k] = tag;
             }
-            y = entered[dir][G];
+            y = sm.entered[dir][G];
         }
         __syncthreads();
         if (hi > stop) hi = dlo;
         if (lo <= e) lo = uhi + 1;
     }
+}
+__global__ __launch_bounds__(kTraceThreads) void viterbi_trace_kernel(VitArgs a) {
+    __shared__ TraceShared<kTraceThreads, kTraceBytes> sm;
+    trace_span<kTraceThreads, kTraceBytes>(a, vit_span(a, blockIdx.x), sm);
+}
+
+// A chunk of the scan (up to 32 tags) by one workgroup of two waves: its forward and its backward chain side by
+// side, then, behind one barrier, its trace: the pointers and the two vectors of the meeting point come back
+// from memory the same workgroup has just written (one launch and one trip through the launch queue less).
+constexpr int kFusedTraceBytes = 2048;
+template <int TP, typename TIN, bool ALIGNED, bool STRUCT>
+__global__ __launch_bounds__(128) void viterbi_chunk_kernel(VitArgs a) {
+    __shared__ double dvec[2][2][TP];
+    __shared__ TraceShared<128, kFusedTraceBytes> sm;
+    const VitSpan sp = vit_span(a, blockIdx.x);
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    if (!sp.empty) viterbi_wave_chain<TP, TIN, ALIGNED, STRUCT, false>(a, sp, wave, threadIdx.x & 63, dvec[wave]);
+    // The barrier orders what the two waves stored before what the trace loads at workgroup scope, which is all it
+    // takes: the waves of a workgroup share their compute unit's vector cache, and stores go through it.  (A fence of
+    // wider scope here would write the whole L2 back once per workgroup: 14 us became 160.)
+    __syncthreads();
+    trace_span<128, kFusedTraceBytes>(a, sp, sm);
 }
 
 template <typename G, typename TIN, bool ALIGNED>
@@ -709,6 +748,10 @@ static hipError_t launch_geo(const VitArgs& a, hipStream_t st) {
 
 template <int TP, typename TIN, bool ALIGNED, bool STRUCT>
 static hipError_t launch_wave_vit(const VitArgs& a, hipStream_t st) {
+    if (a.chunk > 0) {
+        hipLaunchKernelGGL((viterbi_chunk_kernel<TP, TIN, ALIGNED, STRUCT>), dim3(a.B * a.C), dim3(128), 0, st, a);
+        return hipGetLastError();
+    }
     hipLaunchKernelGGL((viterbi_wave_kernel<TP, TIN, ALIGNED, STRUCT>), dim3(2 * a.B * a.C), dim3(64), 0, st, a);
     const hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
