@@ -251,12 +251,12 @@ inline bool lanes_pay_max(int B, int N, int T) {
     return T <= 16 ? B <= 2 * cus : T <= 32 ? B <= cus : 2 * B <= cus;
 }
 // Whether AUTO takes the max-plus scan: where it would pay against the one-wave kernels, unless the chain-wave
-// kernels are quicker still (up to 16 tags they take about 18 us + 0.104 us a position whatever the batch, the
-// scan about 45 us + 0.9 ns a position of the batch: B=64 N=512 70 / 74, B=64 N=768 96 / 84, B=8 N=512 68 / 49,
-// B=128 N=512 70 / 97).
+// kernels are quicker still (up to 16 tags they take about 16 us + 0.084 us a position whatever the batch, the
+// scan about 40 us + 6 ns a position of a sequence + 0.5 ns a position of the batch: B=64 N=512 59 / 61,
+// B=64 N=768 80 / 74, B=8 N=512 58 / 45, B=128 N=512 61 / 76, B=256 N=256 41 / 75).
 inline bool scan_taken_max(int B, int N, int T) {
     if (!scan_pays_max(B, N, T)) return false;
-    return !(lanes_pay_max(B, N, T) && (double)N * (0.104 - 0.0009 * B) < 27.0);
+    return !(lanes_pay_max(B, N, T) && (double)N * (0.078 - 0.0005 * B) < 24.0);
 }
 
 int sum_query(int op, const void* phi, int dt, const int32_t* lengths, int B, int N, int T, float* logZ,
