@@ -219,9 +219,8 @@ __device__ __forceinline__ void lane_chain_wave(const ChainArgs& a, const LaneJo
         float e[NB][16];
         int m;
     };
-    const auto read_tile = [&](unsigned step, Tile& t, unsigned long long word) {
+    const auto read_entries = [&](unsigned step, Tile& t) {
         const unsigned slot = step % S::RING;
-        t.m = __builtin_amdgcn_readfirstlane((int)(unsigned)word);
 #pragma unroll
         for (int bk = 0; bk < NB; ++bk)
 #pragma unroll
@@ -229,6 +228,10 @@ __device__ __forceinline__ void lane_chain_wave(const ChainArgs& a, const LaneJo
                 const float4 v = *reinterpret_cast<const float4*>(&sh.E[slot][urow][16 * (kSplit ? copy : bk) + 4 * g]);
                 t.e[bk][4 * g] = v.x; t.e[bk][4 * g + 1] = v.y; t.e[bk][4 * g + 2] = v.z; t.e[bk][4 * g + 3] = v.w;
             }
+    };
+    const auto read_tile = [&](unsigned step, Tile& t, unsigned long long word) {
+        t.m = __builtin_amdgcn_readfirstlane((int)(unsigned)word);
+        read_entries(step, t);
     };
     // waits for the matrix of `step` (bounded) and reads it; false: it did not come
     const auto fetch = [&](unsigned step, Tile& t) -> bool {
@@ -273,9 +276,10 @@ __device__ __forceinline__ void lane_chain_wave(const ChainArgs& a, const LaneJo
         }
         return fetch(q, nxt) ? 0 : 2;
     };
-    // One step from the matrix in `cur`; meanwhile the matrix of the next step is read into `nxt` if it is
-    // already there (one look at its flag, early enough that the answer is back when the products are done),
-    // else waited for at the end.  Everything the step leaves behind for the other waves is the vector, one
+    // One step from the matrix in `cur`; meanwhile the matrix of the next step is read into `nxt`, whether it is
+    // there or not, so that it comes back under the products: its flag is looked at before (LDS executes a wave's
+    // instructions in order: a flag that was up when it was read means that the reads behind it found the matrix);
+    // if it was not up, the matrix is waited for at the end of the step and read again.  Everything the step leaves behind for the other waves is the vector, one
     // integer and the step count in LDS: the stores to memory are theirs.
     // 0: go on, 1: the step was not accepted (q and the vector are unchanged), 2: the next matrix did not come,
     // 3: that was the last step.
@@ -283,6 +287,8 @@ __device__ __forceinline__ void lane_chain_wave(const ChainArgs& a, const LaneJo
     // wave than masking the write down to one lane.)
     const auto step = [&](const Tile& cur, Tile& nxt) __attribute__((always_inline)) -> int {
         unsigned long long word_next = lds_load_acquire(&sh.ready[(q + 1) % S::RING]);
+        read_entries(q + 1, nxt);
+        __builtin_amdgcn_sched_barrier(0);
         float Ab[4];
         if constexpr (NBLK == 1) {
             Ab[0] = V;
@@ -309,7 +315,10 @@ __device__ __forceinline__ void lane_chain_wave(const ChainArgs& a, const LaneJo
         }
         const int Onew = Oi + cur.m;
         // accepted: every sum in range, and the integer offset far from overflow
-        const unsigned long long inr = __builtin_amdgcn_ballot_w64(sum_in_range(Ssum));
+        // (S in [kSumLo, kSumHi] as one unsigned comparison of its bits: positive floats order like their bit patterns,
+        // negative ones and NaNs fall outside; the comparison leaves the lane mask in scalar registers directly)
+        const unsigned long long inr = __builtin_amdgcn_uicmp(__float_as_uint(Ssum) - __float_as_uint(kSumLo),
+                                                              __float_as_uint(kSumHi) - __float_as_uint(kSumLo), 37 /* unsigned <= */);
         if ((inr & onmask) != onmask || (unsigned)(Onew + (1 << 28)) >= (1u << 29)) return 1;
         // Rescale by the power of two that brings tag 0 into [1/2, 1): any accepted entry serves as the
         // reference (what bounds the vector is the range test above, not where its largest entry lies), and
@@ -322,7 +331,7 @@ __device__ __forceinline__ void lane_chain_wave(const ChainArgs& a, const LaneJo
         sh.VOi[q % kLaneVecRing] = Oi << 1;
         lds_store_release(&sh.done, (int)q);
         if (q == count) return 3;
-        if ((unsigned)__builtin_amdgcn_readfirstlane((int)(word_next >> 32)) >= q + 1) read_tile(q, nxt, word_next);
+        if ((unsigned)__builtin_amdgcn_readfirstlane((int)(word_next >> 32)) >= q + 1) nxt.m = __builtin_amdgcn_readfirstlane((int)(unsigned)word_next);
         else if (!fetch(q, nxt)) return 2;
         return 0;
     };
