@@ -101,6 +101,17 @@ def test_lane_max_chain_that_stops_waiting_goes_on_alone(crf, oracle_mod, polls)
         crf.set_lane_poll_limit(-1)
 
 
+@pytest.mark.parametrize("T,N,dtype", [(32, 1500, "f32"), (48, 700, "f32"), (16, 3000, "bf16"), (64, 300, "f32")])
+def test_lane_max_long_chains(crf, oracle_mod, T, N, dtype):
+    """Hundreds of trips round the rings of matrices and vectors, and a trace that takes several windows of
+    pointers a direction."""
+    phi, _ = workloads.random_case(9950 + T, 2, N, T, scale=2.0, dtype=dtype)
+    lens = torch.tensor([N, N - 37], dtype=torch.int32)
+    check_case(crf, oracle_mod, phi, lens, poison=False, algo=crf.ALGO_SEQUENTIAL_LANES,
+               what=f"lane max long chain T={T} N={N}", queries=("vit",))
+    same_as_sequential(crf, phi, lens, f"lane max long chain T={T} N={N}")
+
+
 def test_lane_max_more_sequences_than_compute_units(crf, oracle_mod):
     """Several workgroups a compute unit (and more than one round of them): 700 short sequences."""
     phi, lens = workloads.random_case(9900, 700, 12, 32, scale=1.0, ragged=True, min_len=0)
