@@ -656,7 +656,9 @@ static int structured_sum(int op, const float* emit, const float* trans, const i
     if ((logZ && !aligned_to(logZ, 4)) || (marginals && !aligned_to(marginals, 16))) return LCCRF_EALIGN;
     const SumWorkspace w = sum_workspace(B, N, T);
     char* base = static_cast<char*>(workspace);
-    if (scan_pays_sum(B, N, T)) {  // the schedule lccrf_auto_algo reports for the dense call of this shape
+    // the schedule lccrf_auto_algo reports for the dense call of this shape
+    const bool lanes = lanes_pay_sum(op, B, N, T) && T <= 48;  // (above, the transition entries no longer fit a producer's registers)
+    if (!lanes && scan_pays_sum(B, N, T)) {
         hipStream_t st = static_cast<hipStream_t>(stream);
         float* Fv = reinterpret_cast<float*>(base + w.Fv);
         double* OF = reinterpret_cast<double*>(base + w.OF);
@@ -680,7 +682,7 @@ static int structured_sum(int op, const float* emit, const float* trans, const i
         op, LCCRF_F32, nullptr, lengths, B, N, T, reinterpret_cast<float*>(base + w.ua),
         reinterpret_cast<float*>(base + w.ub), reinterpret_cast<double*>(base + w.Oa),
         reinterpret_cast<double*>(base + w.Ob), logZ, marginals, static_cast<hipStream_t>(stream), nullptr, false,
-        nullptr, nullptr, nullptr, emit, trans);
+        nullptr, nullptr, nullptr, emit, trans, 0, 0, lanes, g_lane_poll_limit.load(std::memory_order_relaxed));
     return e == hipSuccess ? LCCRF_OK : LCCRF_ELAUNCH;
 }
 

@@ -1069,7 +1069,7 @@ hipError_t launch_sequential_sum(int op, int dtype, const void* phi, const int32
     a.trans = trans;
     if (emit && T > 128) return hipErrorInvalidValue;  // the caller checks structured_supported(T) first
     if (lanes) {
-        if (emit || exact_only || !lane_supported(T)) return hipErrorInvalidValue;
+        if (exact_only || !lane_supported(T)) return hipErrorInvalidValue;
         hipError_t e = launch_lane_pass(false, dtype, a, op == 0, lane_poll_limit, st);
         if (e != hipSuccess) return e;
         if (between) {

@@ -97,10 +97,40 @@ struct LaneJob {
     int first, sdir, count;  // step q consumes the matrix of position first + q sdir
 };
 
+// Where the potentials of sequence b come from: a dense tensor of TIN, or (StructF) trans[s][t] + emit[b][i][t],
+// the single-precision sum the materialised tensor would hold.  at(): one potential; piece(): the four of row s,
+// columns t0 .. t0 + 3 (flat offset off = s T + t0), `fixed` being what fixed_part() returned for that piece.
+struct StructF {};
 template <typename TIN>
-__device__ __forceinline__ float phi2_at(const TIN* phib, size_t TT, int T, int i, int s, int t) {
-    return Elem<TIN>::get(phib + (size_t)i * TT + (size_t)s * T + t) * kLog2e;
-}
+struct LaneSource {
+    static constexpr bool kStruct = false;
+    const TIN* phib;
+    size_t TT;
+    int T;
+    __device__ __forceinline__ LaneSource(const ChainArgs& a, int b)
+        : phib(static_cast<const TIN*>(a.phi) + (size_t)b * a.N * a.T * a.T), TT((size_t)a.T * a.T), T(a.T) {}
+    __device__ __forceinline__ float at(int i, int s, int t) const { return Elem<TIN>::get(phib + (size_t)i * TT + (size_t)s * T + t); }
+    __device__ __forceinline__ void fixed_part(int, float (&f)[4]) const { f[0] = f[1] = f[2] = f[3] = 0.f; }
+    __device__ __forceinline__ void piece(int i, int off, int, const float (&)[4], float (&o)[4]) const {
+        Elem<TIN>::get4(phib + (size_t)i * TT + off, o);
+    }
+};
+template <>
+struct LaneSource<StructF> {
+    static constexpr bool kStruct = true;
+    const float* emb;
+    const float* trans;
+    int T;
+    __device__ __forceinline__ LaneSource(const ChainArgs& a, int b) : emb(a.emit + (size_t)b * a.N * a.T), trans(a.trans), T(a.T) {}
+    __device__ __forceinline__ float at(int i, int s, int t) const { return trans[(size_t)s * T + t] + emb[(size_t)i * T + t]; }
+    __device__ __forceinline__ void fixed_part(int off, float (&f)[4]) const { Elem<float>::get4(trans + off, f); }
+    __device__ __forceinline__ void piece(int i, int, int t0, const float (&f)[4], float (&o)[4]) const {
+        float e[4];
+        Elem<float>::get4(emb + (size_t)i * T + t0, e);
+#pragma unroll
+        for (int k = 0; k < 4; ++k) o[k] = f[k] + e[k];
+    }
+};
 
 // One position in the log domain by the chain wave alone, straight from memory: every log-sum-exp shifted by
 // its own maximum.  lv: the vector that enters step q, base-2 logarithms, lane = tag (-inf from T on), O its
@@ -111,7 +141,7 @@ __device__ __forceinline__ int lane_log_step(const ChainArgs& a, const LaneJob& 
                                              double lz2, int meet_only) {
     const int lane = threadIdx.x & 63, T = a.T, N = a.N, b = jb.b;
     const size_t TT = (size_t)T * T;
-    const TIN* phib = static_cast<const TIN*>(a.phi) + (size_t)b * N * TT;
+    const LaneSource<TIN> src(a, b);
     const size_t vb = (size_t)b * N;
     const int i = jb.first + q * jb.sdir;
     const bool on = lane < T;
@@ -127,13 +157,13 @@ __device__ __forceinline__ int lane_log_step(const ChainArgs& a, const LaneJob& 
     }
     float mx = LCCRF_NEG_INF;
     for (int v = 0; v < T; ++v) {
-        const float x = lane_value(lv, v) + (jb.dir == 0 ? phi2_at(phib, TT, T, i, v, me) : phi2_at(phib, TT, T, i, me, v));
+        const float x = lane_value(lv, v) + (jb.dir == 0 ? src.at(i, v, me) : src.at(i, me, v)) * kLog2e;
         mx = fmaxf(mx, x);
     }
     const float g = finite_or_zero(mx);
     float sum = 0.f;
     for (int v = 0; v < T; ++v) {
-        const float x = lane_value(lv, v) + (jb.dir == 0 ? phi2_at(phib, TT, T, i, v, me) : phi2_at(phib, TT, T, i, me, v));
+        const float x = lane_value(lv, v) + (jb.dir == 0 ? src.at(i, v, me) : src.at(i, me, v)) * kLog2e;
         sum += ex2(x - g);
         if (PASS2 && on) {
             const float m = ex2(x + other + K);
@@ -183,8 +213,7 @@ __device__ __forceinline__ void lane_chain_wave(const ChainArgs& a, const LaneJo
     double O = 0.0;
     if (!PASS2) {
         if (jb.dir == 0) {
-            const TIN* phib = static_cast<const TIN*>(a.phi) + (size_t)b * N * TT;
-            const float x = on ? Elem<TIN>::get(phib + me) * kLog2e : LCCRF_NEG_INF;  // row 0 of the first matrix
+            const float x = on ? LaneSource<TIN>(a, b).at(0, 0, me) * kLog2e : LCCRF_NEG_INF;  // row 0 of the first matrix
             const float d = ceilf(finite_or_zero(xor_max<1, 64>(x)));
             lv = x - d;
             O = (double)d;
@@ -376,7 +405,7 @@ __device__ __forceinline__ void lane_producer_wave(const ChainArgs& a, const Lan
     const int lane = threadIdx.x & 63, T = a.T, N = a.N, b = jb.b;
     const size_t TT = (size_t)T * T;
     const size_t vb = (size_t)b * N;
-    const TIN* phib = static_cast<const TIN*>(a.phi) + (size_t)b * N * TT;
+    const LaneSource<TIN> src(a, b);
     const int nj = w < jb.count ? (jb.count - w + W - 1) / W : 0;  // matrices of this wave: steps w, w + W, ...
     if (nj == 0) return;
     // group m of this lane: entries off .. off + 3 of the matrix (row s, columns t0 .. t0 + 3)
@@ -400,12 +429,16 @@ __device__ __forceinline__ void lane_producer_wave(const ChainArgs& a, const Lan
     }
     float x[PF][NG][4], aux[PF];
     double oo[PF];
+    float fixed[LaneSource<TIN>::kStruct ? NG : 1][4];  // structured potentials: this lane's entries of the transition matrix
+    if constexpr (LaneSource<TIN>::kStruct) {
+#pragma unroll
+        for (int m = 0; m < NG; ++m) src.fixed_part(goff[m], fixed[m]);
+    }
     const auto load = [&](int j, int p) {
         const int q = w + (j < nj ? j : nj - 1) * W;
         const int i = jb.first + q * jb.sdir;
-        const TIN* mat = phib + (size_t)i * TT;
 #pragma unroll
-        for (int m = 0; m < NG; ++m) Elem<TIN>::get4(mat + goff[m], x[p][m]);
+        for (int m = 0; m < NG; ++m) src.piece(i, goff[m], gcol[m], fixed[LaneSource<TIN>::kStruct ? m : 0], x[p][m]);
         if (PASS2) {
             const size_t vp = jb.dir == 0 ? vb + i : vb + i - 1;
             aux[p] = (jb.dir == 0 ? a.ub : a.ua)[vp * T + (lane < T ? lane : 0)];
@@ -585,7 +618,7 @@ __global__ __launch_bounds__(64 * lane_waves(NBLK)) void lane_chain_kernel(Chain
 }
 
 // ---------------------------------------------------------------------------------------
-// Plain potentials, whole sequences, 8 .. 64 tags in multiples of four (16-byte pieces of a row).
+// Dense or structured potentials, whole sequences, 8 .. 64 tags in multiples of four (16-byte pieces of a row).
 bool lane_supported(int T) { return T >= 8 && T <= 64 && T % 4 == 0; }
 
 template <int NBLK, typename TIN, bool PASS2>
@@ -599,6 +632,9 @@ static hipError_t launch_lane_kernel(const ChainArgs& a, int meet_only, int poll
 }
 template <int NBLK>
 static hipError_t launch_lane_nblk(bool second_pass, int dtype, const ChainArgs& a, int meet_only, int poll_limit, hipStream_t st) {
+    if (a.emit)
+        return second_pass ? launch_lane_kernel<NBLK, StructF, true>(a, meet_only, poll_limit, st)
+                           : launch_lane_kernel<NBLK, StructF, false>(a, meet_only, poll_limit, st);
     if (dtype == 0)
         return second_pass ? launch_lane_kernel<NBLK, float, true>(a, meet_only, poll_limit, st)
                            : launch_lane_kernel<NBLK, float, false>(a, meet_only, poll_limit, st);
@@ -607,7 +643,7 @@ static hipError_t launch_lane_nblk(bool second_pass, int dtype, const ChainArgs&
 }
 
 hipError_t launch_lane_pass(bool second_pass, int dtype, const ChainArgs& a, bool meet_only, int poll_limit, hipStream_t st) {
-    if (!lane_supported(a.T) || a.chunk > 0 || a.emit) return hipErrorInvalidValue;
+    if (!lane_supported(a.T) || a.chunk > 0 || (a.emit && (dtype != 0 || !a.trans))) return hipErrorInvalidValue;
     const int mo = meet_only ? 1 : 0;
     if (a.T <= 16) return launch_lane_nblk<1>(second_pass, dtype, a, mo, poll_limit, st);
     if (a.T <= 32) return launch_lane_nblk<2>(second_pass, dtype, a, mo, poll_limit, st);

@@ -80,26 +80,21 @@ struct MaxJob {
     int first, sdir, count;  // step q consumes the matrix of position first + q sdir
 };
 
-// The entries of one matrix this lane works on: v[k] = M(y0 + k, x).  Addresses are clamped into the matrix;
-// what lies outside is masked when it is used (max_entry).
+// The entries of one matrix this lane works on: v[k] = M(y0 + k, x) (T a multiple of four).  Addresses are clamped
+// into the matrix; what lies outside is masked when it is used (max_entry).
 template <int RPL, typename TIN>
-__device__ __forceinline__ void max_load_entries(const TIN* mat, int T, int dir, bool aligned, int y0, int x, float (&v)[RPL]) {
+__device__ __forceinline__ void max_load_entries(const TIN* mat, int T, int dir, int y0, int x, float (&v)[RPL]) {
     const int xc = x < T ? x : T - 1;
     if (dir == 0) {
 #pragma unroll
         for (int k = 0; k < RPL; ++k) v[k] = Elem<TIN>::get(mat + (size_t)(y0 + k < T ? y0 + k : T - 1) * T + xc);
     } else {
         const TIN* row = mat + (size_t)xc * T;
-        if (aligned) {  // T % 4 == 0: 16-byte (8-byte) pieces of the row
 #pragma unroll
-            for (int k = 0; k < RPL; k += 4) {
-                float q[4];
-                Elem<TIN>::get4(row + (y0 + k < T ? y0 + k : T - 4), q);
-                v[k] = q[0]; v[k + 1] = q[1]; v[k + 2] = q[2]; v[k + 3] = q[3];
-            }
-        } else {
-#pragma unroll
-            for (int k = 0; k < RPL; ++k) v[k] = Elem<TIN>::get(row + (y0 + k < T ? y0 + k : T - 1));
+        for (int k = 0; k < RPL; k += 4) {  // 16-byte (8-byte) pieces of the row
+            float q[4];
+            Elem<TIN>::get4(row + (y0 + k < T ? y0 + k : T - 4), q);
+            v[k] = q[0]; v[k + 1] = q[1]; v[k + 2] = q[2]; v[k + 3] = q[3];
         }
     }
 }
@@ -282,7 +277,6 @@ __device__ __forceinline__ void max_chain_wave(const VitArgs& a, const VitSpan& 
         const size_t TT = (size_t)T * T;
         const TIN* phib = static_cast<const TIN*>(a.phi) + (size_t)sp.b * a.N * TT;
         uint8_t* bpb = a.bp + (size_t)sp.b * a.N * T;
-        const bool aligned = (T % 4) == 0;
         int buf = 0;
         sh.own[0][x] = last[x];
         for (; q < count; ++q) {
@@ -291,7 +285,7 @@ __device__ __forceinline__ void max_chain_wave(const VitArgs& a, const VitSpan& 
 #pragma unroll 1
             for (int c = 0; c < RPL; c += S::CH) {  // (a piece of the source tags at a time: few registers)
                 float v[S::CH];
-                max_load_entries<S::CH, TIN>(phib + (size_t)i * TT, T, jb.dir, aligned, y0 + c, x, v);
+                max_load_entries<S::CH, TIN>(phib + (size_t)i * TT, T, jb.dir, y0 + c, x, v);
                 const Best wc = max_pointer_piece<S::CH>(sh.own[buf] + y0 + c, y0 + c, [&](int k) {
                     double2 d;
                     d.x = max_entry(v[k], y0 + c + k < T && x < T);

@@ -22,7 +22,7 @@ hipError_t launch_sequential_sum(int op, int dtype, const void* phi, const int32
                                  unsigned long long* mail = nullptr, int* failed = nullptr, double* logZ64 = nullptr,
                                  const float* emit = nullptr, const float* trans = nullptr, int pair_poll_limit = 0,
                                  int cus = 0, bool lanes = false, int lane_poll_limit = 1 << 16);
-// lanes: the chain-wave / producer-wave kernels of lccrf_lane.hip (lane_chains_supported(T), plain potentials);
+// lanes: the chain-wave / producer-wave kernels of lccrf_lane.hip (lane_chains_supported(T); dense or structured potentials);
 // lane_poll_limit: polls their chain wave spends on a late matrix before it continues in the log domain.
 bool lane_chains_supported(int T);
 // Sampling (lccrf_chain.hip, lccrf_extras.hip): forward chains over whole sequences with every alpha

@@ -93,6 +93,38 @@ def test_structured_agrees_with_dense_call(crf):
     assert torch.equal(y_a, y_b) and torch.equal(s_a, s_b)
 
 
+@pytest.mark.parametrize("T", (20, 24, 32, 40, 48))
+@pytest.mark.parametrize("N", (2, 7, 45))
+def test_structured_on_the_chain_wave_kernels(crf, oracle_mod, T, N):
+    """17 .. 48 tags in multiples of four, batches that leave the chip latency-bound: the sum queries take the
+    chain-wave / producer-wave kernels, whose producers form trans + emit in registers."""
+    assert crf.auto_algo(crf.OP_MARGINALS, 6, N, T) == crf.ALGO_SEQUENTIAL_LANES
+    emit, trans = _make(7250 + 3 * T + N, 6, N, T)
+    lens = torch.tensor([N, 1, max(1, N // 2), 0, max(1, N - 1), min(N, 2)], dtype=torch.int32)
+    _check(crf, oracle_mod, emit, trans, lens, f"structured lanes T={T} N={N}")
+
+
+@pytest.mark.parametrize("T", (32, 48))
+def test_structured_chain_wave_kernels_leave_the_linear_domain(crf, oracle_mod, T):
+    """Forbidden transitions and peaked emissions: positions the scaled single-precision step rejects are taken in
+    the log domain by the chain wave, from trans + emit as well; and with the wait for a matrix made to expire from
+    the host the whole chain is."""
+    N = 60
+    emit, trans = _make(7260 + T, 4, N, T, scale_e=6.0)
+    trans[0, 2] = trans[0, 4] = trans[1, 4] = trans[3, 2] = float("-inf")
+    trans[:, T - 1] = float("-inf")
+    trans[T - 1, T - 1] = 0.0
+    emit[1, 17, :] = -400.0
+    emit[1, 17, 5] = 0.0
+    lens = torch.tensor([N, N, N - 9, 3], dtype=torch.int32)
+    _check(crf, oracle_mod, emit, trans, lens, f"structured lanes -inf and peaks T={T}")
+    crf.set_lane_poll_limit(0)
+    try:
+        _check(crf, oracle_mod, emit, trans, lens, f"structured lanes, poll limit 0, T={T}")
+    finally:
+        crf.set_lane_poll_limit(-1)
+
+
 def test_structured_needs_a_supported_tag_set(crf):
     emit, trans = _make(7300, 2, 6, 129)
     with pytest.raises(crf.LccrfError, match="not available"):
