@@ -298,9 +298,8 @@ int lccrf_semi_markov_log_partition(const void* phi, lccrf_dtype dt, const int32
  *   emit   [B][N][T] float32 (device), 16-byte aligned; trans [T][T] float32 (device), 16-byte aligned.
  * T <= 128 (else LCCRF_ENOTIMPL).  Workspace: lccrf_workspace_bytes of the matching op with LCCRF_F32.
  * The schedule is the one lccrf_auto_algo reports for the matching op and shape (long chains in small
- * batches take the chunked scan, mid-sized batches of 17 .. 48 tags LCCRF_ALGO_SEQUENTIAL_LANES for the sum
- * queries), except that the structured argmax never takes LCCRF_ALGO_SEQUENTIAL_LANES; there is no per-call
- * choice for these three.
+ * batches take the chunked scan, mid-sized batches of up to 48 tags LCCRF_ALGO_SEQUENTIAL_LANES); there is no
+ * per-call choice for these three.
  * Other arguments, outputs and errors as the dense calls.
  */
 int lccrf_log_partition_structured(const float* emit, const float* trans, const int32_t* lengths,

@@ -706,7 +706,7 @@ int lccrf_argmax_structured(const float* emit, const float* trans, const int32_t
     if (!aligned_to(tags, 4) || (best_score && !aligned_to(best_score, 4))) return LCCRF_EALIGN;
     const MaxWorkspace w = max_workspace(B, N, T);
     char* base = static_cast<char*>(workspace);
-    if (scan_pays_max(B, N, T)) {
+    if (scan_taken_max(B, N, T)) {  // the schedule lccrf_auto_algo reports for the dense call of this shape
         hipStream_t st = static_cast<hipStream_t>(stream);
         int32_t* pin = reinterpret_cast<int32_t*>(base + w.pin);
         hipError_t e = lccrf::launch_scan_pins(
@@ -724,7 +724,8 @@ int lccrf_argmax_structured(const float* emit, const float* trans, const int32_t
     const hipError_t e = lccrf::launch_structured_max(emit, trans, lengths, B, N, T,
                                                       reinterpret_cast<uint8_t*>(base + w.bp),
                                                       reinterpret_cast<double*>(base + w.mid), best_score, tags,
-                                                      static_cast<hipStream_t>(stream));
+                                                      static_cast<hipStream_t>(stream), lanes_pay_max(B, N, T),
+                                                      g_lane_poll_limit.load(std::memory_order_relaxed));
     return e == hipSuccess ? LCCRF_OK : LCCRF_ELAUNCH;
 }
 

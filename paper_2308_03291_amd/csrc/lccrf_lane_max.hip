@@ -80,24 +80,71 @@ struct MaxJob {
     int first, sdir, count;  // step q consumes the matrix of position first + q sdir
 };
 
-// The entries of one matrix this lane works on: v[k] = M(y0 + k, x) (T a multiple of four).  Addresses are clamped
-// into the matrix; what lies outside is masked when it is used (max_entry).
-template <int RPL, typename TIN>
-__device__ __forceinline__ void max_load_entries(const TIN* mat, int T, int dir, int y0, int x, float (&v)[RPL]) {
-    const int xc = x < T ? x : T - 1;
-    if (dir == 0) {
+// Where the potentials of sequence b come from: a dense tensor of TIN, or (MaxStructF) trans[s][t] + emit[b][i][t],
+// the single-precision sum the materialised tensor would hold (T a multiple of four either way).
+//   first(t): the score of tag t at position 0;
+//   fixed_part(off, f) / piece(i, off, t0, f, o): the four potentials of row s, columns t0 .. t0 + 3 of position i
+//       (flat offset off = s T + t0), f being what fixed_part returned for that piece;
+//   entries(i, dir, y0, x, v): v[k] = M(y0 + k, x), the entries one lane of the chain wave works on (addresses
+//       clamped into the matrix; what lies outside is masked when it is used, max_entry).
+struct MaxStructF {};
+template <typename TIN>
+struct MaxSource {
+    static constexpr bool kStruct = false;
+    const TIN* phib;
+    size_t TT;
+    int T;
+    __device__ __forceinline__ MaxSource(const VitArgs& a, int b)
+        : phib(static_cast<const TIN*>(a.phi) + (size_t)b * a.N * a.T * a.T), TT((size_t)a.T * a.T), T(a.T) {}
+    __device__ __forceinline__ float first(int t) const { return Elem<TIN>::get(phib + t); }
+    __device__ __forceinline__ void fixed_part(int, float (&f)[4]) const { f[0] = f[1] = f[2] = f[3] = 0.f; }
+    __device__ __forceinline__ void piece(int i, int off, int, const float (&)[4], float (&o)[4]) const {
+        Elem<TIN>::get4(phib + (size_t)i * TT + off, o);
+    }
+    template <int RPL>
+    __device__ __forceinline__ void entries(int i, int dir, int y0, int x, float (&v)[RPL]) const {
+        const TIN* mat = phib + (size_t)i * TT;
+        const int xc = x < T ? x : T - 1;
+        if (dir == 0) {
 #pragma unroll
-        for (int k = 0; k < RPL; ++k) v[k] = Elem<TIN>::get(mat + (size_t)(y0 + k < T ? y0 + k : T - 1) * T + xc);
-    } else {
-        const TIN* row = mat + (size_t)xc * T;
+            for (int k = 0; k < RPL; ++k) v[k] = Elem<TIN>::get(mat + (size_t)(y0 + k < T ? y0 + k : T - 1) * T + xc);
+        } else {
+            const TIN* row = mat + (size_t)xc * T;
 #pragma unroll
-        for (int k = 0; k < RPL; k += 4) {  // 16-byte (8-byte) pieces of the row
-            float q[4];
-            Elem<TIN>::get4(row + (y0 + k < T ? y0 + k : T - 4), q);
-            v[k] = q[0]; v[k + 1] = q[1]; v[k + 2] = q[2]; v[k + 3] = q[3];
+            for (int k = 0; k < RPL; k += 4) {  // 16-byte (8-byte) pieces of the row
+                float q[4];
+                Elem<TIN>::get4(row + (y0 + k < T ? y0 + k : T - 4), q);
+                v[k] = q[0]; v[k + 1] = q[1]; v[k + 2] = q[2]; v[k + 3] = q[3];
+            }
         }
     }
-}
+};
+template <>
+struct MaxSource<MaxStructF> {
+    static constexpr bool kStruct = true;
+    const float* emb;
+    const float* trans;
+    int T;
+    __device__ __forceinline__ MaxSource(const VitArgs& a, int b) : emb(a.emit + (size_t)b * a.N * a.T), trans(a.trans), T(a.T) {}
+    __device__ __forceinline__ float first(int t) const { return trans[t] + emb[t]; }
+    __device__ __forceinline__ void fixed_part(int off, float (&f)[4]) const { Elem<float>::get4(trans + off, f); }
+    __device__ __forceinline__ void piece(int i, int, int t0, const float (&f)[4], float (&o)[4]) const {
+        float e[4];
+        Elem<float>::get4(emb + (size_t)i * T + t0, e);
+#pragma unroll
+        for (int k = 0; k < 4; ++k) o[k] = f[k] + e[k];
+    }
+    template <int RPL>
+    __device__ __forceinline__ void entries(int i, int dir, int y0, int x, float (&v)[RPL]) const {
+        const int xc = x < T ? x : T - 1;
+        const float* er = emb + (size_t)i * T;
+#pragma unroll
+        for (int k = 0; k < RPL; ++k) {
+            const int y = y0 + k < T ? y0 + k : T - 1;
+            v[k] = dir == 0 ? trans[(size_t)y * T + xc] + er[xc] : trans[(size_t)xc * T + y] + er[y];
+        }
+    }
+};
 __device__ __forceinline__ double max_entry(float v, bool inside) { return (double)(inside ? v : LCCRF_NEG_INF); }
 
 // Best source tag per column: the winner of in(y) + M(y, x) over the lane's RPL source tags and then over the
@@ -274,8 +321,7 @@ __device__ __forceinline__ void max_chain_wave(const VitArgs& a, const VitSpan& 
         // The rest of the chain by this wave alone: loads, scores and pointers, a position at a time.  The
         // published vectors stay as they are for the helpers that still work on earlier positions.
         lds_store_release(&sh.stop, (int)q);
-        const size_t TT = (size_t)T * T;
-        const TIN* phib = static_cast<const TIN*>(a.phi) + (size_t)sp.b * a.N * TT;
+        const MaxSource<TIN> src(a, sp.b);
         uint8_t* bpb = a.bp + (size_t)sp.b * a.N * T;
         int buf = 0;
         sh.own[0][x] = last[x];
@@ -285,7 +331,7 @@ __device__ __forceinline__ void max_chain_wave(const VitArgs& a, const VitSpan& 
 #pragma unroll 1
             for (int c = 0; c < RPL; c += S::CH) {  // (a piece of the source tags at a time: few registers)
                 float v[S::CH];
-                max_load_entries<S::CH, TIN>(phib + (size_t)i * TT, T, jb.dir, y0 + c, x, v);
+                src.template entries<S::CH>(i, jb.dir, y0 + c, x, v);
                 const Best wc = max_pointer_piece<S::CH>(sh.own[buf] + y0 + c, y0 + c, [&](int k) {
                     double2 d;
                     d.x = max_entry(v[k], y0 + c + k < T && x < T);
@@ -315,12 +361,13 @@ __device__ __forceinline__ void max_helper_wave(const VitArgs& a, const VitSpan&
     const int nj = w < jb.count ? (jb.count - w + W - 1) / W : 0;  // matrices of this wave: steps w, w + W, ...
     if (nj == 0) return;
     const size_t TT = (size_t)T * T;
-    const TIN* phib = static_cast<const TIN*>(a.phi) + (size_t)sp.b * a.N * TT;
+    const MaxSource<TIN> src(a, sp.b);
     uint8_t* bpb = a.bp + (size_t)sp.b * a.N * T;
     // The matrix is loaded as it lies in memory, piece lane + 64 m of 16 bytes (row s, columns t0 .. t0 + 3), and
     // scattered into the slot in the chain wave's order: entry (y, x) = (s, t) of a forward chain, (t, s) of a
     // backward one, sits at M[slot][k / 2][part TP + x][k % 2] with y = part RPL + k.
     int lidx[NG];  // index (in doubles) of the first entry of piece m in a slot
+    int gcol[NG];  // first column of piece m
     unsigned valid = 0;
 #pragma unroll
     for (int m = 0; m < NG; ++m) {
@@ -331,14 +378,20 @@ __device__ __forceinline__ void max_helper_wave(const VitArgs& a, const VitSpan&
         const int yy = jb.dir == 0 ? s_ : t0, xx = jb.dir == 0 ? t0 : s_;
         const int k = yy % RPL;
         lidx[m] = (((k >> 1) * 65 + (yy / RPL) * TP + xx) << 1) + (k & 1);
+        gcol[m] = t0;
     }
     float raw[2][NG][4];
+    float fixed[MaxSource<TIN>::kStruct ? NG : 1][4];  // structured potentials: this lane's entries of the transition matrix
+    if constexpr (MaxSource<TIN>::kStruct) {
+#pragma unroll
+        for (int m = 0; m < NG; ++m) src.fixed_part(((valid >> m) & 1) ? 4 * (lane + 64 * m) : 0, fixed[m]);
+    }
     const auto load = [&](int j, int p) {
         const int q = w + (j < nj ? j : nj - 1) * W;
         const int i = jb.first + q * jb.sdir;
-        const TIN* mat = phib + (size_t)i * TT;
 #pragma unroll
-        for (int m = 0; m < NG; ++m) Elem<TIN>::get4(mat + (((valid >> m) & 1) ? 4 * (lane + 64 * m) : 0), raw[p][m]);
+        for (int m = 0; m < NG; ++m)
+            src.piece(i, ((valid >> m) & 1) ? 4 * (lane + 64 * m) : 0, gcol[m], fixed[MaxSource<TIN>::kStruct ? m : 0], raw[p][m]);
     };
     // Waits until the flag reaches `target` (true) or the chain wave has gone on alone at or before step `q`
     // (false).  The chain wave always does one or the other: each of its own waits is bounded by the poll limit
@@ -420,7 +473,7 @@ __global__ __launch_bounds__(64 * kMaxWaves) void viterbi_lane_kernel(VitArgs a,
     const int dir = blockIdx.x & 1;
     const VitSpan sp = vit_span(a, blockIdx.x >> 1);
     if (sp.empty) return;
-    const int b = sp.b, N = a.N, T = a.T;
+    const int b = sp.b, T = a.T;
     const int p0 = sp.p0, e = sp.e, h = meeting_point(p0, e);
     MaxJob jb;
     jb.dir = dir;
@@ -433,7 +486,7 @@ __global__ __launch_bounds__(64 * kMaxWaves) void viterbi_lane_kernel(VitArgs a,
         double v0 = ninf;
         if (tid < T) {
             if (dir == 0) {
-                if (sp.t0 == 0) v0 = (double)Elem<TIN>::get(static_cast<const TIN*>(a.phi) + (size_t)b * N * T * T + tid);
+                if (sp.t0 == 0) v0 = (double)MaxSource<TIN>(a, b).first(tid);
                 else v0 = (tid == a.pin[(size_t)b * a.C + sp.c - 1]) ? 0.0 : ninf;
             } else {
                 // a whole sequence may end in any tag; a chunk must end in its pinned tag
@@ -458,7 +511,7 @@ __global__ __launch_bounds__(64 * kMaxWaves) void viterbi_lane_kernel(VitArgs a,
 }
 
 // ---------------------------------------------------------------------------------------
-// Plain potentials, whole sequences, 4 .. 64 tags in multiples of four.
+// Dense or structured potentials, whole sequences, 4 .. 64 tags in multiples of four.
 bool lane_max_supported(int T) { return T >= 4 && T <= 64 && T % 4 == 0; }  // (16-byte pieces of a row)
 
 template <int TP, int ROWS, typename TIN>
@@ -479,7 +532,8 @@ static hipError_t launch_max_T(const VitArgs& a, int poll_limit, hipStream_t st)
 }
 
 hipError_t launch_lane_max_chains(int dtype, const VitArgs& a, int poll_limit, hipStream_t st) {
-    if (!lane_max_supported(a.T) || a.emit || a.chunk > 0) return hipErrorInvalidValue;
+    if (!lane_max_supported(a.T) || a.chunk > 0 || (a.emit && (dtype != 0 || !a.trans))) return hipErrorInvalidValue;
+    if (a.emit) return launch_max_T<MaxStructF>(a, poll_limit, st);
     return dtype == 0 ? launch_max_T<float>(a, poll_limit, st) : launch_max_T<uint16_t>(a, poll_limit, st);
 }
 

@@ -110,7 +110,8 @@ hipError_t launch_sequential_max(int dtype, const void* phi, const int32_t* leng
                                  bool lanes = false, int lane_poll_limit = 1 << 16);
 
 hipError_t launch_structured_max(const float* emit, const float* trans, const int32_t* lengths, int B, int N, int T,
-                                 uint8_t* bp, double* mid, float* best_score, int32_t* tags, hipStream_t st);
+                                 uint8_t* bp, double* mid, float* best_score, int32_t* tags, hipStream_t st,
+                                 bool lanes = false, int lane_poll_limit = 1 << 16);
 
 // Max-plus chunked scan (lccrf_scan.hip): the best score and the tag of the best path at the last
 // position of every chunk (pin: [B][C] ints).  Mx: [B][C][256] doubles, K: [B][C][16] bytes of scratch.

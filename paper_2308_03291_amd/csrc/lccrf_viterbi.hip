@@ -813,9 +813,11 @@ static hipError_t launch_structured_T(const VitArgs& a, hipStream_t st) {
 
 // The same from structured potentials (float emit [B][N][T] + trans [T][T]; T <= 128).
 hipError_t launch_structured_max(const float* emit, const float* trans, const int32_t* lengths, int B, int N, int T,
-                                 uint8_t* bp, double* mid, float* best_score, int32_t* tags, hipStream_t st) {
-    if (T > 128) return hipErrorInvalidValue;
+                                 uint8_t* bp, double* mid, float* best_score, int32_t* tags, hipStream_t st, bool lanes,
+                                 int lane_poll_limit) {
+    if (T > 128 || (lanes && !lane_max_supported(T))) return hipErrorInvalidValue;
     const VitArgs a{nullptr, lengths, B, N, T, bp, mid, best_score, tags, 0, 1, nullptr, emit, trans};
+    if (lanes) return launch_any(0, a, st, true, lane_poll_limit);
     return (T % 4) == 0 ? launch_structured_T<true>(a, st) : launch_structured_T<false>(a, st);
 }
 

@@ -125,6 +125,31 @@ def test_structured_chain_wave_kernels_leave_the_linear_domain(crf, oracle_mod, 
         crf.set_lane_poll_limit(-1)
 
 
+@pytest.mark.parametrize("T", (8, 16, 32, 48))
+def test_structured_argmax_on_the_chain_wave_kernels(crf, oracle_mod, T):
+    """Up to 48 tags in multiples of four the structured argmax takes the max-plus chain-wave kernels where the dense
+    one does (their helpers form trans + emit in registers): tags and scores of the dense call bit for bit, exact
+    ties (integer scores) and forbidden transitions included; and with the wait for a matrix made to expire."""
+    B, N = 6, 70
+    assert crf.auto_algo(crf.OP_ARGMAX, B, N, T) == crf.ALGO_SEQUENTIAL_LANES
+    g = torch.Generator().manual_seed(7280 + T)
+    emit = torch.randint(0, 3, (B, N, T), generator=g).to(torch.float32)
+    trans = torch.randint(0, 3, (T, T), generator=g).to(torch.float32)
+    trans[0, 2] = trans[3, 1] = float("-inf")
+    lens = torch.tensor([N, N - 1, 1, 0, 2, N // 2], dtype=torch.int32)
+    phi = (emit[:, :, None, :] + trans[None, None]).contiguous().cuda()
+    for polls in (-1, 0, 2):
+        crf.set_lane_poll_limit(polls)
+        try:
+            s_a, y_a = crf.lccrf_argmax_structured(emit.cuda(), trans.cuda(), lens.cuda())
+        finally:
+            crf.set_lane_poll_limit(-1)
+        s_b, y_b = crf.lccrf_argmax(phi, lens.cuda(), algo=crf.ALGO_SEQUENTIAL)
+        assert torch.equal(y_a, y_b) and torch.equal(s_a, s_b), f"poll limit {polls}"
+    emit, trans = _make(7290 + T, B, N, T)
+    _check(crf, oracle_mod, emit, trans, lens, f"structured argmax lanes T={T}")
+
+
 def test_structured_needs_a_supported_tag_set(crf):
     emit, trans = _make(7300, 2, 6, 129)
     with pytest.raises(crf.LccrfError, match="not available"):
