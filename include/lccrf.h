@@ -101,7 +101,7 @@ typedef enum {
                                   write the marginals; positions whose sums leave the range of single
                                   precision (or hold -inf) are taken in the log domain.  lccrf_log_partition
                                   and lccrf_marginals at 8 <= T <= 64 with T a multiple of 4.  For
-                                  lccrf_argmax (4 <= T <= 64, T a multiple of 4) the same split in the max-plus
+                                  lccrf_argmax (any T <= 64) the same split in the max-plus
                                   semiring: one wave runs the scores in double precision, the others stream
                                   the potentials and find the pointers; tags and scores are those of
                                   LCCRF_ALGO_SEQUENTIAL bit for bit.  Other queries and tag counts:

@@ -14,7 +14,8 @@
 //       into registers behind the additions of the current step and comes back under its maxima), the vector
 //       published in LDS;
 //   helper waves (1 .. 7): each takes every seventh position: loads the matrix as it lies in memory (coalesced
-//       16-byte pieces, the next matrix in flight while it works on the current one), converts it and scatters
+//       16-byte pieces, or single elements if the tag count is no multiple of four; the next matrix in flight
+//       while it works on the current one), converts it and scatters
 //       it into a ring of LDS slots in the chain wave's order, then, as soon as the vector that enters the
 //       position is published, finds the pointers (smallest best source tag, the tie rule of the other kernels)
 //       from the matrix as it sits in the slot and keeps them for a store one matrix later.  A slot is written
@@ -81,14 +82,24 @@ struct MaxJob {
 };
 
 // Where the potentials of sequence b come from: a dense tensor of TIN, or (MaxStructF) trans[s][t] + emit[b][i][t],
-// the single-precision sum the materialised tensor would hold (T a multiple of four either way).
+// the single-precision sum the materialised tensor would hold.  AL: T is a multiple of four (16-byte loads).
 //   first(t): the score of tag t at position 0;
-//   fixed_part(off, f) / piece(i, off, t0, f, o): the four potentials of row s, columns t0 .. t0 + 3 of position i
-//       (flat offset off = s T + t0), f being what fixed_part returned for that piece;
+//   fixed_part(s, t0, f) / piece(i, s, t0, f, o): the four potentials of row s, columns t0 .. t0 + 3 of position i
+//       (columns clamped to the matrix if T is no multiple of four: the caller masks them), f being what fixed_part
+//       returned for that piece;
 //   entries(i, dir, y0, x, v): v[k] = M(y0 + k, x), the entries one lane of the chain wave works on (addresses
 //       clamped into the matrix; what lies outside is masked when it is used, max_entry).
 struct MaxStructF {};
-template <typename TIN>
+template <typename E, bool AL>
+__device__ __forceinline__ void max_load4(const E* row, int T, int t0, float (&o)[4]) {  // row[t0 .. t0 + 3]
+    if constexpr (AL) {
+        Elem<E>::get4(row + t0, o);
+    } else {
+#pragma unroll
+        for (int k = 0; k < 4; ++k) o[k] = Elem<E>::get(row + (t0 + k < T ? t0 + k : T - 1));
+    }
+}
+template <typename TIN, bool AL>
 struct MaxSource {
     static constexpr bool kStruct = false;
     const TIN* phib;
@@ -97,9 +108,9 @@ struct MaxSource {
     __device__ __forceinline__ MaxSource(const VitArgs& a, int b)
         : phib(static_cast<const TIN*>(a.phi) + (size_t)b * a.N * a.T * a.T), TT((size_t)a.T * a.T), T(a.T) {}
     __device__ __forceinline__ float first(int t) const { return Elem<TIN>::get(phib + t); }
-    __device__ __forceinline__ void fixed_part(int, float (&f)[4]) const { f[0] = f[1] = f[2] = f[3] = 0.f; }
-    __device__ __forceinline__ void piece(int i, int off, int, const float (&)[4], float (&o)[4]) const {
-        Elem<TIN>::get4(phib + (size_t)i * TT + off, o);
+    __device__ __forceinline__ void fixed_part(int, int, float (&f)[4]) const { f[0] = f[1] = f[2] = f[3] = 0.f; }
+    __device__ __forceinline__ void piece(int i, int s, int t0, const float (&)[4], float (&o)[4]) const {
+        max_load4<TIN, AL>(phib + (size_t)i * TT + (size_t)s * T, T, t0, o);
     }
     template <int RPL>
     __device__ __forceinline__ void entries(int i, int dir, int y0, int x, float (&v)[RPL]) const {
@@ -111,26 +122,26 @@ struct MaxSource {
         } else {
             const TIN* row = mat + (size_t)xc * T;
 #pragma unroll
-            for (int k = 0; k < RPL; k += 4) {  // 16-byte (8-byte) pieces of the row
+            for (int k = 0; k < RPL; k += 4) {
                 float q[4];
-                Elem<TIN>::get4(row + (y0 + k < T ? y0 + k : T - 4), q);
+                max_load4<TIN, AL>(row, T, AL ? (y0 + k < T ? y0 + k : T - 4) : y0 + k, q);
                 v[k] = q[0]; v[k + 1] = q[1]; v[k + 2] = q[2]; v[k + 3] = q[3];
             }
         }
     }
 };
-template <>
-struct MaxSource<MaxStructF> {
+template <bool AL>
+struct MaxSource<MaxStructF, AL> {
     static constexpr bool kStruct = true;
     const float* emb;
     const float* trans;
     int T;
     __device__ __forceinline__ MaxSource(const VitArgs& a, int b) : emb(a.emit + (size_t)b * a.N * a.T), trans(a.trans), T(a.T) {}
     __device__ __forceinline__ float first(int t) const { return trans[t] + emb[t]; }
-    __device__ __forceinline__ void fixed_part(int off, float (&f)[4]) const { Elem<float>::get4(trans + off, f); }
+    __device__ __forceinline__ void fixed_part(int s, int t0, float (&f)[4]) const { max_load4<float, AL>(trans + (size_t)s * T, T, t0, f); }
     __device__ __forceinline__ void piece(int i, int, int t0, const float (&f)[4], float (&o)[4]) const {
         float e[4];
-        Elem<float>::get4(emb + (size_t)i * T + t0, e);
+        max_load4<float, AL>(emb + (size_t)i * T, T, t0, e);
 #pragma unroll
         for (int k = 0; k < 4; ++k) o[k] = f[k] + e[k];
     }
@@ -220,7 +231,7 @@ __device__ __forceinline__ double max_over_parts(double r) {
 }
 
 // The chain wave.
-template <int TP, int ROWS, typename TIN>
+template <int TP, int ROWS, typename TIN, bool AL>
 __device__ __forceinline__ void max_chain_wave(const VitArgs& a, const VitSpan& sp, const MaxJob& jb, MaxShared<TP, ROWS>& sh,
                                                double* mid, int poll_limit) {
     using S = MaxShape<TP, ROWS>;
@@ -321,7 +332,7 @@ __device__ __forceinline__ void max_chain_wave(const VitArgs& a, const VitSpan& 
         // The rest of the chain by this wave alone: loads, scores and pointers, a position at a time.  The
         // published vectors stay as they are for the helpers that still work on earlier positions.
         lds_store_release(&sh.stop, (int)q);
-        const MaxSource<TIN> src(a, sp.b);
+        const MaxSource<TIN, AL> src(a, sp.b);
         uint8_t* bpb = a.bp + (size_t)sp.b * a.N * T;
         int buf = 0;
         sh.own[0][x] = last[x];
@@ -351,7 +362,7 @@ __device__ __forceinline__ void max_chain_wave(const VitArgs& a, const VitSpan& 
 }
 
 // A helper wave.
-template <int TP, int ROWS, typename TIN>
+template <int TP, int ROWS, typename TIN, bool AL>
 __device__ __forceinline__ void max_helper_wave(const VitArgs& a, const VitSpan& sp, const MaxJob& jb, MaxShared<TP, ROWS>& sh,
                                                 int w, int poll_limit) {
     using S = MaxShape<TP, ROWS>;
@@ -360,38 +371,39 @@ __device__ __forceinline__ void max_helper_wave(const VitArgs& a, const VitSpan&
     const int part = lane / TP, x = lane % TP, y0 = part * RPL;
     const int nj = w < jb.count ? (jb.count - w + W - 1) / W : 0;  // matrices of this wave: steps w, w + W, ...
     if (nj == 0) return;
-    const size_t TT = (size_t)T * T;
-    const MaxSource<TIN> src(a, sp.b);
+    const MaxSource<TIN, AL> src(a, sp.b);
     uint8_t* bpb = a.bp + (size_t)sp.b * a.N * T;
     // The matrix is loaded as it lies in memory, piece lane + 64 m of 16 bytes (row s, columns t0 .. t0 + 3), and
     // scattered into the slot in the chain wave's order: entry (y, x) = (s, t) of a forward chain, (t, s) of a
     // backward one, sits at M[slot][k / 2][part TP + x][k % 2] with y = part RPL + k.
     int lidx[NG];  // index (in doubles) of the first entry of piece m in a slot
-    int gcol[NG];  // first column of piece m
+    int grow[NG], gcol[NG];  // row and first column of piece m
     unsigned valid = 0;
+    const int Q = (T + 3) / 4;  // pieces a row (the last one of a row is cut off at T if T is no multiple of four)
 #pragma unroll
     for (int m = 0; m < NG; ++m) {
-        const int off = 4 * (lane + 64 * m);
-        const bool ok = off < (int)TT;
+        const int g = lane + 64 * m;
+        const bool ok = g < T * Q;
         valid |= ok ? (1u << m) : 0u;
-        const int s_ = (ok ? off : 0) / T, t0 = (ok ? off : 0) % T;
+        const int s_ = (ok ? g : 0) / Q, t0 = 4 * ((ok ? g : 0) % Q);
         const int yy = jb.dir == 0 ? s_ : t0, xx = jb.dir == 0 ? t0 : s_;
         const int k = yy % RPL;
         lidx[m] = (((k >> 1) * 65 + (yy / RPL) * TP + xx) << 1) + (k & 1);
+        grow[m] = s_;
         gcol[m] = t0;
     }
     float raw[2][NG][4];
-    float fixed[MaxSource<TIN>::kStruct ? NG : 1][4];  // structured potentials: this lane's entries of the transition matrix
-    if constexpr (MaxSource<TIN>::kStruct) {
+    float fixed[MaxSource<TIN, AL>::kStruct ? NG : 1][4];  // structured potentials: this lane's entries of the transition matrix
+    if constexpr (MaxSource<TIN, AL>::kStruct) {
 #pragma unroll
-        for (int m = 0; m < NG; ++m) src.fixed_part(((valid >> m) & 1) ? 4 * (lane + 64 * m) : 0, fixed[m]);
+        for (int m = 0; m < NG; ++m) src.fixed_part(grow[m], gcol[m], fixed[m]);
     }
     const auto load = [&](int j, int p) {
         const int q = w + (j < nj ? j : nj - 1) * W;
         const int i = jb.first + q * jb.sdir;
 #pragma unroll
         for (int m = 0; m < NG; ++m)
-            src.piece(i, ((valid >> m) & 1) ? 4 * (lane + 64 * m) : 0, gcol[m], fixed[MaxSource<TIN>::kStruct ? m : 0], raw[p][m]);
+            src.piece(i, grow[m], gcol[m], fixed[MaxSource<TIN, AL>::kStruct ? m : 0], raw[p][m]);
     };
     // Waits until the flag reaches `target` (true) or the chain wave has gone on alone at or before step `q`
     // (false).  The chain wave always does one or the other: each of its own waits is bounded by the poll limit
@@ -425,13 +437,16 @@ __device__ __forceinline__ void max_helper_wave(const VitArgs& a, const VitSpan&
 #pragma unroll
         for (int m = 0; m < NG; ++m)
             if ((valid >> m) & 1) {
+                double d[4];
+#pragma unroll
+                for (int k = 0; k < 4; ++k) d[k] = max_entry(raw[p][m][k], AL || gcol[m] + k < T);  // (-inf past the last column)
                 if (jb.dir == 0) {  // four columns of one source tag: 16 bytes apart
 #pragma unroll
-                    for (int k = 0; k < 4; ++k) Ms[lidx[m] + 2 * k] = (double)raw[p][m][k];
+                    for (int k = 0; k < 4; ++k) Ms[lidx[m] + 2 * k] = d[k];
                 } else {            // four source tags of one column: two pairs
                     double2 d0, d1;
-                    d0.x = (double)raw[p][m][0]; d0.y = (double)raw[p][m][1];
-                    d1.x = (double)raw[p][m][2]; d1.y = (double)raw[p][m][3];
+                    d0.x = d[0]; d0.y = d[1];
+                    d1.x = d[2]; d1.y = d[3];
                     *reinterpret_cast<double2*>(Ms + lidx[m]) = d0;
                     *reinterpret_cast<double2*>(Ms + lidx[m] + 130) = d1;
                 }
@@ -463,7 +478,7 @@ __device__ __forceinline__ void max_helper_wave(const VitArgs& a, const VitSpan&
     flush();
 }
 
-template <int TP, int ROWS, typename TIN>
+template <int TP, int ROWS, typename TIN, bool AL>
 __global__ __launch_bounds__(64 * kMaxWaves) void viterbi_lane_kernel(VitArgs a, int poll_limit) {
     using S = MaxShape<TP, ROWS>;
     extern __shared__ __attribute__((aligned(16))) unsigned char max_smem[];
@@ -486,7 +501,7 @@ __global__ __launch_bounds__(64 * kMaxWaves) void viterbi_lane_kernel(VitArgs a,
         double v0 = ninf;
         if (tid < T) {
             if (dir == 0) {
-                if (sp.t0 == 0) v0 = (double)MaxSource<TIN>(a, b).first(tid);
+                if (sp.t0 == 0) v0 = (double)MaxSource<TIN, AL>(a, b).first(tid);
                 else v0 = (tid == a.pin[(size_t)b * a.C + sp.c - 1]) ? 0.0 : ninf;
             } else {
                 // a whole sequence may end in any tag; a chunk must end in its pinned tag
@@ -504,37 +519,41 @@ __global__ __launch_bounds__(64 * kMaxWaves) void viterbi_lane_kernel(VitArgs a,
     __syncthreads();
     if (wv == 0) {
         __builtin_amdgcn_s_setprio(3);
-        max_chain_wave<TP, ROWS, TIN>(a, sp, jb, sh, mid, poll_limit);
+        max_chain_wave<TP, ROWS, TIN, AL>(a, sp, jb, sh, mid, poll_limit);
     } else {
-        max_helper_wave<TP, ROWS, TIN>(a, sp, jb, sh, wv - 1, poll_limit);
+        max_helper_wave<TP, ROWS, TIN, AL>(a, sp, jb, sh, wv - 1, poll_limit);
     }
 }
 
 // ---------------------------------------------------------------------------------------
-// Dense or structured potentials, whole sequences, 4 .. 64 tags in multiples of four.
-bool lane_max_supported(int T) { return T >= 4 && T <= 64 && T % 4 == 0; }  // (16-byte pieces of a row)
+// Dense or structured potentials, whole sequences, up to 64 tags.
+bool lane_max_supported(int T) { return T >= 1 && T <= 64; }
 
-template <int TP, int ROWS, typename TIN>
+template <int TP, int ROWS, typename TIN, bool AL>
 static hipError_t launch_max_kernel(const VitArgs& a, int poll_limit, hipStream_t st) {
     const size_t bytes = sizeof(MaxShared<TP, ROWS>);
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&viterbi_lane_kernel<TP, ROWS, TIN>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&viterbi_lane_kernel<TP, ROWS, TIN, AL>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL((viterbi_lane_kernel<TP, ROWS, TIN>), dim3(2 * a.B * a.C), dim3(64 * kMaxWaves), bytes, st, a, poll_limit);
+    hipLaunchKernelGGL((viterbi_lane_kernel<TP, ROWS, TIN, AL>), dim3(2 * a.B * a.C), dim3(64 * kMaxWaves), bytes, st, a, poll_limit);
     return hipGetLastError();
 }
-template <typename TIN>
+template <typename TIN, bool AL>
 static hipError_t launch_max_T(const VitArgs& a, int poll_limit, hipStream_t st) {
-    if (a.T <= 16) return launch_max_kernel<16, 16, TIN>(a, poll_limit, st);
-    if (a.T <= 32) return launch_max_kernel<32, 32, TIN>(a, poll_limit, st);
-    if (a.T <= 48) return launch_max_kernel<64, 48, TIN>(a, poll_limit, st);
-    return launch_max_kernel<64, 64, TIN>(a, poll_limit, st);
+    if (a.T <= 16) return launch_max_kernel<16, 16, TIN, AL>(a, poll_limit, st);
+    if (a.T <= 32) return launch_max_kernel<32, 32, TIN, AL>(a, poll_limit, st);
+    if (a.T <= 48) return launch_max_kernel<64, 48, TIN, AL>(a, poll_limit, st);
+    return launch_max_kernel<64, 64, TIN, AL>(a, poll_limit, st);
+}
+template <typename TIN>
+static hipError_t launch_max_src(const VitArgs& a, int poll_limit, hipStream_t st) {
+    return (a.T % 4) == 0 ? launch_max_T<TIN, true>(a, poll_limit, st) : launch_max_T<TIN, false>(a, poll_limit, st);
 }
 
 hipError_t launch_lane_max_chains(int dtype, const VitArgs& a, int poll_limit, hipStream_t st) {
     if (!lane_max_supported(a.T) || a.chunk > 0 || (a.emit && (dtype != 0 || !a.trans))) return hipErrorInvalidValue;
-    if (a.emit) return launch_max_T<MaxStructF>(a, poll_limit, st);
-    return dtype == 0 ? launch_max_T<float>(a, poll_limit, st) : launch_max_T<uint16_t>(a, poll_limit, st);
+    if (a.emit) return launch_max_src<MaxStructF>(a, poll_limit, st);
+    return dtype == 0 ? launch_max_src<float>(a, poll_limit, st) : launch_max_src<uint16_t>(a, poll_limit, st);
 }
 
 }  // namespace lccrf
