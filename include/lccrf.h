@@ -100,7 +100,7 @@ typedef enum {
                                   other waves of its workgroup stream and exponentiate the potentials and
                                   write the marginals; positions whose sums leave the range of single
                                   precision (or hold -inf) are taken in the log domain.  lccrf_log_partition
-                                  and lccrf_marginals at 8 <= T <= 64 with T a multiple of 4.  For
+                                  and lccrf_marginals at 8 <= T <= 48, and at 52, 56, 60 and 64 tags.  For
                                   lccrf_argmax (any T <= 64) the same split in the max-plus
                                   semiring: one wave runs the scores in double precision, the others stream
                                   the potentials and find the pointers; tags and scores are those of

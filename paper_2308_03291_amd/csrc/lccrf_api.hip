@@ -224,12 +224,20 @@ inline bool scan_pays_sample(int B, int N, int T) { return T <= 32 && scan_pays_
 // itself; the one-wave and four-wave kernels take 0.7 .. 0.9 us a position, the scan some 30 us plus 2.9 ns a
 // position of the whole batch at 17 .. 32 tags.  Measured (marginals, us; lanes / scan / sequential):
 // B=128 N=256 T=32 102 / 122 / 197, B=256 N=256 T=32 168 / 246 / 227, B=32 N=64 T=32 38 / 40 / 57,
-// B=32 N=256 T=32 98 / 61 / 193, B=128 N=128 T=48 92 / 216 / 133, B=64 N=64 T=48 47 / 78 / 73.  Up to 16 tags the
-// scan is cheaper wherever the batch is small enough for these kernels; above 48 tags the second pass does not
-// pay (its producers spill), the first still does (B=32 N=256 T=64 log-partition 76 / 121 / 108).
+// B=32 N=256 T=32 98 / 61 / 193, B=128 N=128 T=48 92 / 216 / 133, B=64 N=64 T=48 47 / 78 / 73.  Above 48 tags the
+// second pass does not pay (its producers spill), the first still does (B=32 N=256 T=64 log-partition 76 / 121 / 108).
+// With 8 .. 16 tags they take about 15.5 us plus 0.24 us a position, up to one sequence a compute unit (two
+// workgroups of twelve waves each), against 11 us plus 0.6 us a position for the one-wave kernels and some 27 us plus
+// 0.75 ns a position of the whole batch for the scan (marginals, lanes / scan / sequential: B=128 N=32 T=13
+// 23 / - / 32, B=256 N=128 T=16 50 / 53 / 98, B=128 N=128 T=9 46 / 41 / 99, B=32 N=256 T=8 75 / 38 / 170,
+// B=512 N=64 T=16 62 / - / 55).
 inline bool lanes_pay_sum(int op, int B, int N, int T) {
-    if (!lccrf::lane_chains_supported(T) || T <= 16) return false;
+    if (!lccrf::lane_chains_supported(T)) return false;
     const int cus = current_device_cus();
+    if (T <= 16) {
+        if (B > cus || N < 16) return false;
+        return !scan_pays_sum(B, N, T) || (double)N * (0.24 - 0.00075 * B) < 10.0;
+    }
     if (T <= 32) {
         if (B > cus) return false;
         return !scan_pays_sum(B, N, T) || (double)N * (0.35 - 0.0029 * B) < 18.0;

@@ -322,7 +322,7 @@ __device__ __forceinline__ void bwd_advance(ChainSmem<G>& sm, int& buf, int& nst
 }
 
 // ---------------------------------------------------------------------------------------
-// Forward half chain for 32 < T <= 128 (T % 4 == 0) with the tile turned through LDS memory.
+// Forward half chain for 32 < T <= 128 with the tile turned through LDS memory.
 //
 // With rows spread over all waves, the forward step has to merge the waves' partial column sums
 // through LDS behind a second barrier while all but the column waves wait.  Here every tile is written
@@ -333,14 +333,14 @@ __device__ __forceinline__ void bwd_advance(ChainSmem<G>& sm, int& buf, int& nst
 // Lane l of wave w holds rows (l % LPR) + LPR k, k < 4, of columns (256 / LPR) w + 4 (l / LPR) + j, j < 4.
 template <typename G, bool ALIGNED, int PF>
 constexpr bool half_turns() {
-    return ((G::LPR == 32 && G::WAVES == 16) || (G::LPR == 16 && G::WAVES == 4)) && G::ITEMS == 4 && ALIGNED && PF == 4;
+    return ((G::LPR == 32 && G::WAVES == 16) || (G::LPR == 16 && G::WAVES == 4)) && G::ITEMS == 4 && PF == 4;
 }
 // LDS floats of the two turned tiles of geometry G: TCAP rows of TCAP + 4 floats each (the padding keeps 16-byte
 // accesses free of bank conflicts).
 template <typename G>
 constexpr int turn_floats() { return 2 * G::TCAP * (G::TCAP + 4); }
 
-template <typename G, typename TIN, int PF>
+template <typename G, typename TIN, int PF, bool ALIGNED>
 __device__ __forceinline__ void forward_half_turned(ChainSmem<G>& sm, float* __restrict__ tiles, const ChainArgs& a,
                                                     const Span& sp, int tid) {
     static_assert(G::ITEMS == 4 && PF == 4 && G::LPR * 4 == G::TCAP && G::WAVES * (256 / G::LPR) == G::TCAP,
@@ -367,8 +367,9 @@ __device__ __forceinline__ void forward_half_turned(ChainSmem<G>& sm, float* __r
     int buf = 0, nstep = 0;
     if (n > 0) {
         float ring[PF][4][4];
-        auto load = [&](int i, int slot) { load_tile<G, TIN, true>(phib + (size_t)i * TT, T, c4, r0, ring[slot]); };
+        auto load = [&](int i, int slot) { load_tile<G, TIN, ALIGNED>(phib + (size_t)i * TT, T, c4, r0, ring[slot], b != a.B - 1 || i != N - 1); };
         auto to_lds = [&](int slot, int wb) {
+            settle_tile<G, ALIGNED>(ring[slot], T, c4);
 #pragma unroll
             for (int k = 0; k < 4; ++k)
                 *reinterpret_cast<float4*>(&tiles[(wb * ROWS + r0 + LPR * k) * STRIDE + c4]) =
@@ -468,15 +469,15 @@ __device__ __forceinline__ void forward_half_turned(ChainSmem<G>& sm, float* __r
     if (tid == 0) a.Oa[vb + h] = O;
 }
 
-// The forward chain of the second pass in the same turned form (four-wave geometry, 32 < T <= 64, T % 4 == 0):
+// The forward chain of the second pass in the same turned form (four-wave geometry, 32 < T <= 64):
 // it continues alpha past the meeting point and writes the marginals of positions h + 1 .. e.  Measured on
 // 128 ragged sequences of 48 tags this chain, with its second barrier a step, was what the second pass waited
 // for (82 us alone against 65 us for the backward chain alone).  A lane writes the marginals of its four rows
 // of four columns; the sixteen lanes of a column quad cover sixteen consecutive rows.
 template <typename G, bool ALIGNED>
-constexpr bool marginal_turns() { return G::LPR == 16 && G::WAVES == 4 && G::ITEMS == 4 && ALIGNED; }
+constexpr bool marginal_turns() { return G::LPR == 16 && G::WAVES == 4 && G::ITEMS == 4; }
 
-template <typename G, typename TIN>
+template <typename G, typename TIN, bool ALIGNED>
 __device__ __forceinline__ void forward_marginal_turned(ChainSmem<G>& sm, float* __restrict__ tiles, const ChainArgs& a,
                                                         const Span& sp, int tid, double lz2, bool feasible) {
     constexpr int PF = 4, LPR = G::LPR, ROWS = G::TCAP, STRIDE = G::TCAP + 4;
@@ -490,7 +491,7 @@ __device__ __forceinline__ void forward_marginal_turned(ChainSmem<G>& sm, float*
     float* mub = a.mu + (size_t)b * N * TT;
     const bool exact_only = a.exact_only != 0;
     const int rowl = lane % LPR, colw = (256 / LPR) * wave + 4 * (lane / LPR);
-    const int colc = colw < T ? colw : T - 4;  // (clamped: where the stored backward vector is read)
+    const int colc = colw < T ? colw : (ALIGNED ? T - 4 : 0);  // (clamped: where the stored backward vector is read)
     const int kk = 2 * (lane & 1) + ((lane >> 1) & 1);  // the column reduce4_over_lanes leaves in this lane
 
     double O = a.Oa[vb + h];
@@ -501,12 +502,18 @@ __device__ __forceinline__ void forward_marginal_turned(ChainSmem<G>& sm, float*
     int buf = 0, nstep = 0;
     float ring[PF][4][4], aux[PF][4];
     double ob[PF];
-    auto load = [&](int i, int slot) { load_tile<G, TIN, true>(phib + (size_t)i * TT, T, c4, r0, ring[slot]); };
+    auto load = [&](int i, int slot) { load_tile<G, TIN, ALIGNED>(phib + (size_t)i * TT, T, c4, r0, ring[slot], b != a.B - 1 || i != N - 1); };
     auto load_aux = [&](int i, int slot) {  // beta_i of this lane's columns and its offset
-        Elem<float>::get4(a.ub + (vb + i) * T + colc, aux[slot]);
+        if constexpr (ALIGNED) {
+            Elem<float>::get4(a.ub + (vb + i) * T + colc, aux[slot]);
+        } else {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) aux[slot][j] = a.ub[(vb + i) * T + (colc + j < T ? colc + j : colc)];
+        }
         ob[slot] = a.Ob[vb + i];
     };
     auto to_lds = [&](int slot, int wb) {
+        settle_tile<G, ALIGNED>(ring[slot], T, c4);
 #pragma unroll
         for (int k = 0; k < 4; ++k)
             *reinterpret_cast<float4*>(&tiles[(wb * ROWS + r0 + LPR * k) * STRIDE + c4]) =
@@ -562,7 +569,7 @@ __device__ __forceinline__ void forward_marginal_turned(ChainSmem<G>& sm, float*
                     const float e0 = ex2(__builtin_fmaf(q.x, kLog2e, uac)), e1 = ex2(__builtin_fmaf(q.y, kLog2e, uac));
                     const float e2 = ex2(__builtin_fmaf(q.z, kLog2e, uac)), e3 = ex2(__builtin_fmaf(q.w, kLog2e, uac));
                     ls[0] += e0; ls[1] += e1; ls[2] += e2; ls[3] += e3;
-                    store4<true, false>(mu_out, T, rowl + LPR * k, colw, e0 * gm[0], e1 * gm[1], e2 * gm[2], e3 * gm[3]);
+                    store4<ALIGNED, false>(mu_out, T, rowl + LPR * k, colw, e0 * gm[0], e1 * gm[1], e2 * gm[2], e3 * gm[3]);
                 }
                 float tot = (ls[0] * gm[0] + ls[1] * gm[1]) + (ls[2] * gm[2] + ls[3] * gm[3]);
                 tot = xor_sum<1, 64>(tot);
@@ -606,7 +613,7 @@ __device__ __forceinline__ void forward_marginal_turned(ChainSmem<G>& sm, float*
                         ex[j] = ex2(v[k][j] - g[j]);
                         Sl[j] += ex[j];
                     }
-                    store4<true, false>(mu_out, T, rowl + LPR * k, colw, ex[0] * gx[0], ex[1] * gx[1], ex[2] * gx[2], ex[3] * gx[3]);
+                    store4<ALIGNED, false>(mu_out, T, rowl + LPR * k, colw, ex[0] * gx[0], ex[1] * gx[1], ex[2] * gx[2], ex[3] * gx[3]);
                 }
                 float tot = (Sl[0] * gx[0] + Sl[1] * gx[1]) + (Sl[2] * gx[2] + Sl[3] * gx[3]);
                 tot = xor_sum<1, 64>(tot);
@@ -659,7 +666,7 @@ __global__ __launch_bounds__(G::W) void chain_half_kernel(ChainArgs a) {
     if constexpr (half_turns<G, ALIGNED, PF>() && !STRUCT) {  // (structured tiles are formed in registers: nothing to turn)
         if (dir == 0) {
             extern __shared__ __attribute__((aligned(16))) float turn_tiles[];
-            forward_half_turned<G, TIN, PF>(sm, turn_tiles, a, sp, tid);
+            forward_half_turned<G, TIN, PF, ALIGNED>(sm, turn_tiles, a, sp, tid);
             return;
         }
     }
@@ -677,17 +684,20 @@ __global__ __launch_bounds__(G::W) void chain_half_kernel(ChainArgs a) {
     float tr[CAN_STRUCT ? ITEMS : 1][4];
     if constexpr (CAN_STRUCT) {
         load_tile<G, float, ALIGNED>(a.trans, T, c4, r0, tr);
+        settle_tile<G, ALIGNED>(tr, T, c4);
     }
     auto load = [&](int i, int slot) {
         if constexpr (CAN_STRUCT) {
             load_emit4<ALIGNED>(emb + (size_t)i * T, T, c4, ring[slot][0]);
             return;
         }
-        load_tile<G, TIN, ALIGNED>(phib + (size_t)i * TT, T, c4, r0, ring[slot]);
+        load_tile<G, TIN, ALIGNED>(phib + (size_t)i * TT, T, c4, r0, ring[slot], b != a.B - 1 || i != N - 1);
     };
     auto tile_ready = [&](int slot) {  // turns a slot that holds emissions into the tile
         if constexpr (CAN_STRUCT) {
             add_trans<ITEMS>(ring[slot], tr);
+        } else {
+            settle_tile<G, ALIGNED>(ring[slot], T, c4);
         }
     };
 
@@ -788,7 +798,7 @@ __global__ __launch_bounds__(G::W) void chain_marginal_kernel(ChainArgs a) {
     if constexpr (marginal_turns<G, ALIGNED>() && !STRUCT) {
         if (dir == 0) {
             extern __shared__ __attribute__((aligned(16))) float turn_tiles[];
-            forward_marginal_turned<G, TIN>(sm, turn_tiles, a, sp, tid, lz2, feasible);
+            forward_marginal_turned<G, TIN, ALIGNED>(sm, turn_tiles, a, sp, tid, lz2, feasible);
             return;
         }
     }
@@ -801,17 +811,20 @@ __global__ __launch_bounds__(G::W) void chain_marginal_kernel(ChainArgs a) {
     float tr[CAN_STRUCT ? ITEMS : 1][4];
     if constexpr (CAN_STRUCT) {
         load_tile<G, float, ALIGNED>(a.trans, T, c4, r0, tr);
+        settle_tile<G, ALIGNED>(tr, T, c4);
     }
     auto load_phi = [&](int i, int slot) {
         if constexpr (CAN_STRUCT) {
             load_emit4<ALIGNED>(emb + (size_t)i * T, T, c4, ring[slot][0]);
             return;
         }
-        load_tile<G, TIN, ALIGNED>(phib + (size_t)i * TT, T, c4, r0, ring[slot]);
+        load_tile<G, TIN, ALIGNED>(phib + (size_t)i * TT, T, c4, r0, ring[slot], b != a.B - 1 || i != N - 1);
     };
     auto tile_ready = [&](int slot) {
         if constexpr (CAN_STRUCT) {
             add_trans<ITEMS>(ring[slot], tr);
+        } else {
+            settle_tile<G, ALIGNED>(ring[slot], T, c4);
         }
     };
 

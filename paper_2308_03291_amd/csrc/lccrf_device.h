@@ -35,13 +35,26 @@ __device__ __forceinline__ float bf16_to_f32(uint16_t h) {
 
 typedef float vec4f __attribute__((ext_vector_type(4)));
 typedef unsigned int vec2u __attribute__((ext_vector_type(2)));
+// The same vectors at an address that is aligned like a single element only (rows of a matrix whose tag count is no
+// multiple of four): types that promise the compiler no more than that.  (Vector types, not structs of four members:
+// a struct's load is taken apart into its members early, and does not always come together again.)
+typedef vec4f vec4f_anywhere __attribute__((aligned(4)));
+typedef vec2u vec2u_anywhere __attribute__((aligned(2)));
 __device__ __forceinline__ void stream_store4(float* p, float a0, float a1, float a2, float a3) {
     __builtin_nontemporal_store(vec4f{a0, a1, a2, a3}, reinterpret_cast<vec4f*>(p));
+}
+
+__device__ __forceinline__ void store4_anywhere(float* p, float a0, float a1, float a2, float a3) {
+    *reinterpret_cast<vec4f_anywhere*>(p) = vec4f{a0, a1, a2, a3};
 }
 
 template <typename TIN> struct Elem;
 template <> struct Elem<float> {
     static __device__ __forceinline__ float get(const float* p) { return *p; }
+    static __device__ __forceinline__ void get4_anywhere(const float* p, float (&o)[4]) {
+        const vec4f v = *reinterpret_cast<const vec4f_anywhere*>(p);
+        o[0] = v[0]; o[1] = v[1]; o[2] = v[2]; o[3] = v[3];
+    }
     static __device__ __forceinline__ void get4(const float* p, float (&o)[4]) {
         const float4 v = *reinterpret_cast<const float4*>(p);
         o[0] = v.x; o[1] = v.y; o[2] = v.z; o[3] = v.w;
@@ -57,6 +70,13 @@ template <> struct Elem<float> {
 };
 template <> struct Elem<uint16_t> {
     static __device__ __forceinline__ float get(const uint16_t* p) { return bf16_to_f32(*p); }
+    static __device__ __forceinline__ void get4_anywhere(const uint16_t* p, float (&o)[4]) {
+        const vec2u v = *reinterpret_cast<const vec2u_anywhere*>(p);
+        o[0] = __uint_as_float(v[0] << 16);
+        o[1] = __uint_as_float(v[0] & 0xffff0000u);
+        o[2] = __uint_as_float(v[1] << 16);
+        o[3] = __uint_as_float(v[1] & 0xffff0000u);
+    }
     static __device__ __forceinline__ void get4(const uint16_t* p, float (&o)[4]) {
         const uint2 v = *reinterpret_cast<const uint2*>(p);
         o[0] = __uint_as_float(v.x << 16);
@@ -87,24 +107,60 @@ struct Geo {
     static_assert(RPP * ITEMS_ >= TCAP || RPP * ITEMS_ >= 1, "rows not covered");
 };
 
+// Columns c4 .. c4 + 3 of row s of a T x T matrix whose rows lie anywhere an element may (T no multiple of four).
+// A thread whose row or columns lie outside the matrix takes the last row, or the columns from 0 on, instead.  The
+// four elements come as one load wherever four elements follow in the matrix: those past the end of the row are then
+// the first of the next row.  Only the piece that ends the matrix (the last columns of the last row) is loaded element
+// by element, and that only if nothing follows the matrix in memory (FOLLOWED says that something does: another
+// matrix of the tensor; then the load is the same instruction in every thread, with no branch around it).
+// settle_row4() makes of what was loaded the piece every consumer may rely on; nothing here touches the loaded
+// values, so the loads stay in flight.
+template <typename TIN, bool FOLLOWED>
+__device__ __forceinline__ void load_row4_anywhere(const TIN* __restrict__ mat, int T, int s, int c4, float (&o)[4]) {
+    const int cc = c4 < T ? c4 : 0;
+    const int off = (s < T ? s : T - 1) * T + cc;
+    if (FOLLOWED || off + 4 <= T * T) {
+        Elem<TIN>::get4_anywhere(mat + off, o);
+    } else {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) o[j] = Elem<TIN>::get(mat + off + (cc + j < T ? j : 0));
+    }
+}
+// The entries of such a piece that lie past the end of the row become copies of its first entry: data of the row
+// itself, which the thread works on anyway.
+__device__ __forceinline__ void settle_row4(float (&o)[4], int T, int c4) {
+    const int cc = c4 < T ? c4 : 0;
+#pragma unroll
+    for (int j = 1; j < 4; ++j) o[j] = cc + j < T ? o[j] : o[0];
+}
+
 // Issue the loads of this thread's part of one matrix.  Addresses are clamped into the
 // matrix, so every lane issues the same loads with no branch around them, and nothing here
-// touches the loaded values: the loads stay in flight until mask_tile() is applied where the
-// tile is consumed.
+// touches the loaded values: the loads stay in flight until the tile is consumed.  There settle_tile()
+// comes first (it does nothing when the tag count is a multiple of four), then whatever the kernel does
+// about the entries outside the matrix (mask_tile(), or weights that drop them).
 template <typename G, typename TIN, bool ALIGNED>
 __device__ __forceinline__ void load_tile(const TIN* __restrict__ mat, int T, int c4, int r0,
-                                          float (&v)[G::ITEMS][4]) {
+                                          float (&v)[G::ITEMS][4], bool followed = false) {
 #pragma unroll
     for (int k = 0; k < G::ITEMS; ++k) {
         const int s = r0 + k * G::RPP;
-        const TIN* row = mat + (size_t)(s < T ? s : T - 1) * T;
         if (ALIGNED) {
+            const TIN* row = mat + (size_t)(s < T ? s : T - 1) * T;
             if (G::TCAP > 64) Elem<TIN>::get4_stream(row + (c4 < T ? c4 : T - 4), v[k]);  // T % 4 == 0 here, so T >= 4
             else Elem<TIN>::get4(row + (c4 < T ? c4 : T - 4), v[k]);
+        } else if (followed) {  // (the same for the whole workgroup: a scalar branch)
+            load_row4_anywhere<TIN, true>(mat, T, s, c4, v[k]);
         } else {
-#pragma unroll
-            for (int j = 0; j < 4; ++j) v[k][j] = Elem<TIN>::get(row + (c4 + j < T ? c4 + j : T - 1));
+            load_row4_anywhere<TIN, false>(mat, T, s, c4, v[k]);
         }
+    }
+}
+template <typename G, bool ALIGNED>
+__device__ __forceinline__ void settle_tile(float (&v)[G::ITEMS][4], int T, int c4) {
+    if constexpr (!ALIGNED) {
+#pragma unroll
+        for (int k = 0; k < G::ITEMS; ++k) settle_row4(v[k], T, c4);
     }
 }
 
@@ -117,9 +173,10 @@ template <bool ALIGNED>
 __device__ __forceinline__ void load_emit4(const float* __restrict__ emit_row, int T, int c4, float (&o)[4]) {
     if (ALIGNED) {
         Elem<float>::get4(emit_row + (c4 < T ? c4 : T - 4), o);
-    } else {
+    } else {  // (the columns a settled tile of the transition matrix holds: see load_row4_anywhere)
+        const int cc = c4 < T ? c4 : 0;
 #pragma unroll
-        for (int j = 0; j < 4; ++j) o[j] = emit_row[c4 + j < T ? c4 + j : T - 1];
+        for (int j = 0; j < 4; ++j) o[j] = emit_row[cc + j < T ? cc + j : cc];
     }
 }
 template <int ROWS>
@@ -154,6 +211,8 @@ __device__ __forceinline__ void store_tile(float* __restrict__ mat, int T, int c
             float* p = mat + (size_t)s * T + c4;
             if (ALIGNED) {
                 *reinterpret_cast<float4*>(p) = make_float4(v[k][0], v[k][1], v[k][2], v[k][3]);
+            } else if (c4 + 4 <= T) {
+                store4_anywhere(p, v[k][0], v[k][1], v[k][2], v[k][3]);
             } else {
 #pragma unroll
                 for (int j = 0; j < 4; ++j)
@@ -432,11 +491,12 @@ __device__ __forceinline__ void store4(float* __restrict__ mu_out, int T, int s,
         if (ALIGNED) {
             if (STREAM) stream_store4(p, a0, a1, a2, a3);
             else *reinterpret_cast<float4*>(p) = make_float4(a0, a1, a2, a3);
+        } else if (c4 + 4 <= T) {
+            store4_anywhere(p, a0, a1, a2, a3);
         } else {
             p[0] = a0;
             if (c4 + 1 < T) p[1] = a1;
             if (c4 + 2 < T) p[2] = a2;
-            if (c4 + 3 < T) p[3] = a3;
         }
     }
 }

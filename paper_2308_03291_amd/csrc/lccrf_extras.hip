@@ -198,8 +198,8 @@ __global__ __launch_bounds__(G::W) void entropy_half_kernel(ChainArgs a) {
     float ring[PF][ITEMS][4];
     float qring[QPF][QITEMS][4];
     auto load = [&](int i, int slot) {
-        load_tile<G, TIN, ALIGNED>(phib + (size_t)i * TT, T, c4, r0, ring[slot]);
-        if constexpr (QRING) load_tile<G, TIN, ALIGNED>(psib + (size_t)i * TT, T, c4, r0, qring[slot]);
+        load_tile<G, TIN, ALIGNED>(phib + (size_t)i * TT, T, c4, r0, ring[slot], b != a.B - 1 || i != N - 1);
+        if constexpr (QRING) load_tile<G, TIN, ALIGNED>(psib + (size_t)i * TT, T, c4, r0, qring[slot], b != a.B - 1 || i != N - 1);
     };
     // what an edge adds to the carried expectation (modes 1 and 2)
     auto edge_term = [&](int i, int slot, int k, const float (&x)[4], float (&f)[4]) {
@@ -232,6 +232,8 @@ __global__ __launch_bounds__(G::W) void entropy_half_kernel(ChainArgs a) {
     if (dir == 0) {
         walk<PF>(1, h, +1, load, [&](int i, int slot) {
             float (&x)[ITEMS][4] = ring[slot];
+            settle_tile<G, ALIGNED>(x, T, c4);
+            if constexpr (QRING) settle_tile<G, ALIGNED>(qring[slot], T, c4);
             const float d = shift();
             O += (double)d;
             float c = 0.f;
@@ -359,6 +361,8 @@ __global__ __launch_bounds__(G::W) void entropy_half_kernel(ChainArgs a) {
     } else {
         walk<PF>(e, h + 1, -1, load, [&](int i, int slot) {
             float (&y)[ITEMS][4] = ring[slot];
+            settle_tile<G, ALIGNED>(y, T, c4);
+            if constexpr (QRING) settle_tile<G, ALIGNED>(qring[slot], T, c4);
             const float d = shift();
             O += (double)d;
             float c = 0.f;

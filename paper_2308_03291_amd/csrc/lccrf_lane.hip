@@ -100,8 +100,25 @@ struct LaneJob {
 // Where the potentials of sequence b come from: a dense tensor of TIN, or (StructF) trans[s][t] + emit[b][i][t],
 // the single-precision sum the materialised tensor would hold.  at(): one potential; piece(): the four of row s,
 // columns t0 .. t0 + 3 (flat offset off = s T + t0), `fixed` being what fixed_part() returned for that piece.
+// AL: the tag count is a multiple of four and every piece lies on a 16-byte boundary.  Otherwise the rows start at any
+// multiple of the element size: the last piece of a row is moved back to end where the row ends (it overlaps the
+// piece before it; the entries both hold are the same numbers, written to the same places), and a piece is loaded and
+// stored through types that promise the compiler no more than the element's alignment.
 struct StructF {};
-template <typename TIN>
+template <bool AL, typename E>
+__device__ __forceinline__ void lane_load4(const E* p, float (&o)[4]) {
+    if constexpr (AL) Elem<E>::get4(p, o);
+    else Elem<E>::get4_anywhere(p, o);
+}
+template <bool AL>
+__device__ __forceinline__ void lane_store4(float* p, float a, float b, float c, float d) {
+    if constexpr (AL) {
+        *reinterpret_cast<float4*>(p) = make_float4(a, b, c, d);
+    } else {
+        store4_anywhere(p, a, b, c, d);
+    }
+}
+template <typename TIN, bool AL>
 struct LaneSource {
     static constexpr bool kStruct = false;
     const TIN* phib;
@@ -110,23 +127,23 @@ struct LaneSource {
     __device__ __forceinline__ LaneSource(const ChainArgs& a, int b)
         : phib(static_cast<const TIN*>(a.phi) + (size_t)b * a.N * a.T * a.T), TT((size_t)a.T * a.T), T(a.T) {}
     __device__ __forceinline__ float at(int i, int s, int t) const { return Elem<TIN>::get(phib + (size_t)i * TT + (size_t)s * T + t); }
-    __device__ __forceinline__ void fixed_part(int, float (&f)[4]) const { f[0] = f[1] = f[2] = f[3] = 0.f; }
+    __device__ __forceinline__ void fixed_part(int, int, float (&f)[4]) const { f[0] = f[1] = f[2] = f[3] = 0.f; }
     __device__ __forceinline__ void piece(int i, int off, int, const float (&)[4], float (&o)[4]) const {
-        Elem<TIN>::get4(phib + (size_t)i * TT + off, o);
+        lane_load4<AL>(phib + (size_t)i * TT + off, o);
     }
 };
-template <>
-struct LaneSource<StructF> {
+template <bool AL>
+struct LaneSource<StructF, AL> {
     static constexpr bool kStruct = true;
     const float* emb;
     const float* trans;
     int T;
     __device__ __forceinline__ LaneSource(const ChainArgs& a, int b) : emb(a.emit + (size_t)b * a.N * a.T), trans(a.trans), T(a.T) {}
     __device__ __forceinline__ float at(int i, int s, int t) const { return trans[(size_t)s * T + t] + emb[(size_t)i * T + t]; }
-    __device__ __forceinline__ void fixed_part(int off, float (&f)[4]) const { Elem<float>::get4(trans + off, f); }
+    __device__ __forceinline__ void fixed_part(int off, int, float (&f)[4]) const { lane_load4<AL>(trans + off, f); }
     __device__ __forceinline__ void piece(int i, int, int t0, const float (&f)[4], float (&o)[4]) const {
         float e[4];
-        Elem<float>::get4(emb + (size_t)i * T + t0, e);
+        lane_load4<AL>(emb + (size_t)i * T + t0, e);
 #pragma unroll
         for (int k = 0; k < 4; ++k) o[k] = f[k] + e[k];
     }
@@ -136,12 +153,12 @@ struct LaneSource<StructF> {
 // its own maximum.  lv: the vector that enters step q, base-2 logarithms, lane = tag (-inf from T on), O its
 // offset; on return lv is the result less the integer shift that is returned (its maximum then lies in (-1, 0]).
 // Writes what the step owes to memory: the marginals of its position (second pass), the stored vector (first).
-template <typename TIN, bool PASS2>
+template <typename TIN, bool AL, bool PASS2>
 __device__ __forceinline__ int lane_log_step(const ChainArgs& a, const LaneJob& jb, int q, float& lv, double O,
                                              double lz2, int meet_only) {
     const int lane = threadIdx.x & 63, T = a.T, N = a.N, b = jb.b;
     const size_t TT = (size_t)T * T;
-    const LaneSource<TIN> src(a, b);
+    const LaneSource<TIN, AL> src(a, b);
     const size_t vb = (size_t)b * N;
     const int i = jb.first + q * jb.sdir;
     const bool on = lane < T;
@@ -186,14 +203,14 @@ __device__ __forceinline__ int lane_log_step(const ChainArgs& a, const LaneJob& 
 }
 
 // The log-domain tail: steps q0 .. count - 1 of the job.  Returns with lv / O the last vector.
-template <typename TIN, bool PASS2>
+template <typename TIN, bool AL, bool PASS2>
 __device__ __forceinline__ void lane_log_tail(const ChainArgs& a, const LaneJob& jb, int q0, float& lv, double& O,
                                               double lz2, int meet_only) {
-    for (int q = q0; q < jb.count; ++q) O += (double)lane_log_step<TIN, PASS2>(a, jb, q, lv, O, lz2, meet_only);
+    for (int q = q0; q < jb.count; ++q) O += (double)lane_log_step<TIN, AL, PASS2>(a, jb, q, lv, O, lz2, meet_only);
 }
 
 // The chain wave.
-template <int NBLK, typename TIN, bool PASS2>
+template <int NBLK, typename TIN, bool AL, bool PASS2>
 __device__ __forceinline__ void lane_chain_wave(const ChainArgs& a, const LaneJob& jb, LaneShared<NBLK>& sh, double lz2,
                                                 bool feasible, int meet_only, int poll_limit) {
     using S = LaneShape<NBLK>;
@@ -213,7 +230,7 @@ __device__ __forceinline__ void lane_chain_wave(const ChainArgs& a, const LaneJo
     double O = 0.0;
     if (!PASS2) {
         if (jb.dir == 0) {
-            const float x = on ? LaneSource<TIN>(a, b).at(0, 0, me) * kLog2e : LCCRF_NEG_INF;  // row 0 of the first matrix
+            const float x = on ? LaneSource<TIN, AL>(a, b).at(0, 0, me) * kLog2e : LCCRF_NEG_INF;  // row 0 of the first matrix
             const float d = ceilf(finite_or_zero(xor_max<1, 64>(x)));
             lv = x - d;
             O = (double)d;
@@ -281,7 +298,7 @@ __device__ __forceinline__ void lane_chain_wave(const ChainArgs& a, const LaneJo
     const auto slow_steps = [&](Tile& nxt) -> int {
         float lvs = lane < T ? lg2(V) : LCCRF_NEG_INF;
         for (int n = 0;; ++n) {
-            const int d = lane_log_step<TIN, PASS2>(a, jb, (int)q, lvs, O0 + (double)Oi, lz2, meet_only);
+            const int d = lane_log_step<TIN, AL, PASS2>(a, jb, (int)q, lvs, O0 + (double)Oi, lz2, meet_only);
             Oi += d;
             float lall = lvs;  // every copy of the vector gets its tag's value
             if constexpr (kSplit) {
@@ -383,7 +400,7 @@ __device__ __forceinline__ void lane_chain_wave(const ChainArgs& a, const LaneJo
     lv = !on ? LCCRF_NEG_INF : carried ? lv_carry : lg2(V);
     if (tail) {
         if (lane == 0) lds_store_release(&sh.stop, (int)q);
-        lane_log_tail<TIN, PASS2>(a, jb, (int)q, lv, O, lz2, meet_only);
+        lane_log_tail<TIN, AL, PASS2>(a, jb, (int)q, lv, O, lz2, meet_only);
     } else if (!PASS2 && meet_only && count > 0) {
         // a log-partition call keeps the vectors of the meeting position only: the last of this chain
         if (on) (jb.dir == 0 ? a.ua : a.ub)[(vb + jb.h) * T + lane] = lv;
@@ -397,7 +414,7 @@ __device__ __forceinline__ void lane_chain_wave(const ChainArgs& a, const LaneJo
 }
 
 // A producer wave.
-template <int NBLK, typename TIN, bool PASS2>
+template <int NBLK, typename TIN, bool AL, bool PASS2>
 __device__ __forceinline__ void lane_producer_wave(const ChainArgs& a, const LaneJob& jb, LaneShared<NBLK>& sh, int w,
                                                    double lz2, int meet_only, int poll_limit) {
     using S = LaneShape<NBLK>;
@@ -405,19 +422,22 @@ __device__ __forceinline__ void lane_producer_wave(const ChainArgs& a, const Lan
     const int lane = threadIdx.x & 63, T = a.T, N = a.N, b = jb.b;
     const size_t TT = (size_t)T * T;
     const size_t vb = (size_t)b * N;
-    const LaneSource<TIN> src(a, b);
+    const LaneSource<TIN, AL> src(a, b);
     const int nj = w < jb.count ? (jb.count - w + W - 1) / W : 0;  // matrices of this wave: steps w, w + W, ...
     if (nj == 0) return;
-    // group m of this lane: entries off .. off + 3 of the matrix (row s, columns t0 .. t0 + 3)
+    // group m of this lane: piece g = lane + 64 m of the matrix, row s = g / Q, columns t0 .. t0 + 3, Q pieces a row:
+    // t0 = 4 (g % Q), but the last piece of a row ends with the row (T - 4: only a tag count that is no multiple of
+    // four moves it)
     int goff[NG], grow[NG], gcol[NG], laddr[NG][4];
     unsigned valid = 0;
+    const int Q = (T + 3) >> 2;
 #pragma unroll
     for (int m = 0; m < NG; ++m) {
-        const int off = 4 * (lane + 64 * m);
-        const bool ok = off < (int)TT;
+        const int g = lane + 64 * m;
+        const bool ok = g < T * Q;
         valid |= ok ? (1u << m) : 0u;
-        goff[m] = ok ? off : 0;
-        const int s = goff[m] / T, t0 = goff[m] % T;
+        const int s = ok ? g / Q : 0, t0 = ok ? min(4 * (g % Q), T - 4) : 0;
+        goff[m] = s * T + t0;
         grow[m] = s;
         gcol[m] = t0;
 #pragma unroll
@@ -429,16 +449,16 @@ __device__ __forceinline__ void lane_producer_wave(const ChainArgs& a, const Lan
     }
     float x[PF][NG][4], aux[PF];
     double oo[PF];
-    float fixed[LaneSource<TIN>::kStruct ? NG : 1][4];  // structured potentials: this lane's entries of the transition matrix
-    if constexpr (LaneSource<TIN>::kStruct) {
+    float fixed[LaneSource<TIN, AL>::kStruct ? NG : 1][4];  // structured potentials: this lane's entries of the transition matrix
+    if constexpr (LaneSource<TIN, AL>::kStruct) {
 #pragma unroll
-        for (int m = 0; m < NG; ++m) src.fixed_part(goff[m], fixed[m]);
+        for (int m = 0; m < NG; ++m) src.fixed_part(goff[m], gcol[m], fixed[m]);
     }
     const auto load = [&](int j, int p) {
         const int q = w + (j < nj ? j : nj - 1) * W;
         const int i = jb.first + q * jb.sdir;
 #pragma unroll
-        for (int m = 0; m < NG; ++m) src.piece(i, goff[m], gcol[m], fixed[LaneSource<TIN>::kStruct ? m : 0], x[p][m]);
+        for (int m = 0; m < NG; ++m) src.piece(i, goff[m], gcol[m], fixed[LaneSource<TIN, AL>::kStruct ? m : 0], x[p][m]);
         if (PASS2) {
             const size_t vp = jb.dir == 0 ? vb + i : vb + i - 1;
             aux[p] = (jb.dir == 0 ? a.ub : a.ua)[vp * T + (lane < T ? lane : 0)];
@@ -501,10 +521,10 @@ __device__ __forceinline__ void lane_producer_wave(const ChainArgs& a, const Lan
             for (int m = 0; m < NG; ++m)
                 if ((valid >> m) & 1) {
                     const float rf = rowf[grow[m]];
-                    const float4 cf = *reinterpret_cast<const float4*>(colf + gcol[m]);
-                    *reinterpret_cast<float4*>(mu_i + goff[m]) =
-                        make_float4(x[p][m][0] * rf * cf.x, x[p][m][1] * rf * cf.y, x[p][m][2] * rf * cf.z,
-                                    x[p][m][3] * rf * cf.w);
+                    float cf[4];
+                    lane_load4<AL>(colf + gcol[m], cf);
+                    lane_store4<AL>(mu_i + goff[m], x[p][m][0] * rf * cf[0], x[p][m][1] * rf * cf[1], x[p][m][2] * rf * cf[2],
+                                    x[p][m][3] * rf * cf[3]);
                 }
         }
         if (!PASS2 && !meet_only) {
@@ -535,7 +555,7 @@ __device__ __forceinline__ void lane_producer_wave(const ChainArgs& a, const Lan
     }
 }
 
-template <int NBLK, typename TIN, bool PASS2>
+template <int NBLK, typename TIN, bool AL, bool PASS2>
 __global__ __launch_bounds__(64 * lane_waves(NBLK)) void lane_chain_kernel(ChainArgs a, int meet_only, int poll_limit) {
     using S = LaneShape<NBLK>;
     constexpr int kLaneWaves = lane_waves(NBLK);
@@ -554,15 +574,13 @@ __global__ __launch_bounds__(64 * lane_waves(NBLK)) void lane_chain_kernel(Chain
     // Marginals that carry no edge are zero: the positions past the end (forward workgroup) and rows
     // 1 .. T - 1 of position 0 (backward workgroup).  Cleared by the wave that has no other work
     // (by everyone for an empty sequence).
+    const auto zero_floats = [&](float* d, size_t n, int first, int threads) {  // n floats from d on, by threads first, first + 1, ...
+        for (size_t k = first; k < n / 4; k += threads) lane_store4<AL>(d + 4 * k, 0.f, 0.f, 0.f, 0.f);
+        if (!AL && first < (int)(n % 4)) d[n - 1 - first] = 0.f;
+    };
     const auto clear_edgeless = [&](int first_thread, int threads) {
-        if (jb.dir == 0) {
-            float4* p = reinterpret_cast<float4*>(a.mu + (vb + L) * TT);
-            const size_t n4 = (size_t)(N - L) * TT / 4;
-            for (size_t k = tid - first_thread; k < n4; k += threads) p[k] = make_float4(0.f, 0.f, 0.f, 0.f);
-        } else if (L > 0) {
-            float4* p = reinterpret_cast<float4*>(a.mu + vb * TT + T);
-            for (size_t k = tid - first_thread; k < (TT - T) / 4; k += threads) p[k] = make_float4(0.f, 0.f, 0.f, 0.f);
-        }
+        if (jb.dir == 0) zero_floats(a.mu + (vb + L) * TT, (size_t)(N - L) * TT, tid - first_thread, threads);
+        else if (L > 0) zero_floats(a.mu + vb * TT + T, TT - T, tid - first_thread, threads);
     };
     if (L == 0) {
         if (PASS2) clear_edgeless(0, 64 * kLaneWaves);
@@ -590,8 +608,7 @@ __global__ __launch_bounds__(64 * lane_waves(NBLK)) void lane_chain_kernel(Chain
         if (jb.dir == 0 && tid == 0 && a.logZ) a.logZ[b] = (float)(lz2 * kLn2);
         if (!feasible) {  // no path has a finite score: every marginal is zero
             for (int q = 0; q < jb.count; ++q) {
-                float4* p = reinterpret_cast<float4*>(a.mu + (vb + jb.first + q * jb.sdir) * TT);
-                for (size_t k = tid; k < TT / 4; k += 64 * kLaneWaves) p[k] = make_float4(0.f, 0.f, 0.f, 0.f);
+                zero_floats(a.mu + (vb + jb.first + q * jb.sdir) * TT, TT, tid, 64 * kLaneWaves);
             }
             if (jb.dir == 1 && tid < T) a.mu[vb * TT + tid] = 0.f;
             clear_edgeless(0, 64 * kLaneWaves);
@@ -610,36 +627,43 @@ __global__ __launch_bounds__(64 * lane_waves(NBLK)) void lane_chain_kernel(Chain
     __syncthreads();
     if (wv == 0) {
         __builtin_amdgcn_s_setprio(3);
-        lane_chain_wave<NBLK, TIN, PASS2>(a, jb, sh, lz2, feasible, meet_only, poll_limit);
+        lane_chain_wave<NBLK, TIN, AL, PASS2>(a, jb, sh, lz2, feasible, meet_only, poll_limit);
     } else {
         if (PASS2 && wv == 4) clear_edgeless(4 * 64, 64);  // (the producer that shares the chain's SIMD)
-        lane_producer_wave<NBLK, TIN, PASS2>(a, jb, sh, wv - 1, lz2, meet_only, poll_limit);
+        lane_producer_wave<NBLK, TIN, AL, PASS2>(a, jb, sh, wv - 1, lz2, meet_only, poll_limit);
     }
 }
 
 // ---------------------------------------------------------------------------------------
-// Dense or structured potentials, whole sequences, 8 .. 64 tags in multiples of four (16-byte pieces of a row).
-bool lane_supported(int T) { return T >= 8 && T <= 64 && T % 4 == 0; }
+// Dense or structured potentials, whole sequences, 8 .. 64 tags: multiples of four (16-byte pieces of a row) at every
+// size, other counts (element loads) up to 48.
+bool lane_supported(int T) { return T >= 8 && T <= 64 && (T % 4 == 0 || T <= 48); }
 
-template <int NBLK, typename TIN, bool PASS2>
+template <int NBLK, typename TIN, bool AL, bool PASS2>
 static hipError_t launch_lane_kernel(const ChainArgs& a, int meet_only, int poll_limit, hipStream_t st) {
     const size_t bytes = sizeof(LaneShared<NBLK>);
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&lane_chain_kernel<NBLK, TIN, PASS2>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&lane_chain_kernel<NBLK, TIN, AL, PASS2>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL((lane_chain_kernel<NBLK, TIN, PASS2>), dim3(2 * a.B), dim3(64 * lane_waves(NBLK)), bytes, st, a, meet_only, poll_limit);
+    hipLaunchKernelGGL((lane_chain_kernel<NBLK, TIN, AL, PASS2>), dim3(2 * a.B), dim3(64 * lane_waves(NBLK)), bytes, st, a, meet_only, poll_limit);
     return hipGetLastError();
+}
+template <int NBLK, bool AL>
+static hipError_t launch_lane_al(bool second_pass, int dtype, const ChainArgs& a, int meet_only, int poll_limit, hipStream_t st) {
+    if (a.emit)
+        return second_pass ? launch_lane_kernel<NBLK, StructF, AL, true>(a, meet_only, poll_limit, st)
+                           : launch_lane_kernel<NBLK, StructF, AL, false>(a, meet_only, poll_limit, st);
+    if (dtype == 0)
+        return second_pass ? launch_lane_kernel<NBLK, float, AL, true>(a, meet_only, poll_limit, st)
+                           : launch_lane_kernel<NBLK, float, AL, false>(a, meet_only, poll_limit, st);
+    return second_pass ? launch_lane_kernel<NBLK, uint16_t, AL, true>(a, meet_only, poll_limit, st)
+                       : launch_lane_kernel<NBLK, uint16_t, AL, false>(a, meet_only, poll_limit, st);
 }
 template <int NBLK>
 static hipError_t launch_lane_nblk(bool second_pass, int dtype, const ChainArgs& a, int meet_only, int poll_limit, hipStream_t st) {
-    if (a.emit)
-        return second_pass ? launch_lane_kernel<NBLK, StructF, true>(a, meet_only, poll_limit, st)
-                           : launch_lane_kernel<NBLK, StructF, false>(a, meet_only, poll_limit, st);
-    if (dtype == 0)
-        return second_pass ? launch_lane_kernel<NBLK, float, true>(a, meet_only, poll_limit, st)
-                           : launch_lane_kernel<NBLK, float, false>(a, meet_only, poll_limit, st);
-    return second_pass ? launch_lane_kernel<NBLK, uint16_t, true>(a, meet_only, poll_limit, st)
-                       : launch_lane_kernel<NBLK, uint16_t, false>(a, meet_only, poll_limit, st);
+    if (a.T % 4 == 0) return launch_lane_al<NBLK, true>(second_pass, dtype, a, meet_only, poll_limit, st);
+    if constexpr (NBLK <= 3) return launch_lane_al<NBLK, false>(second_pass, dtype, a, meet_only, poll_limit, st);
+    return hipErrorInvalidValue;
 }
 
 hipError_t launch_lane_pass(bool second_pass, int dtype, const ChainArgs& a, bool meet_only, int poll_limit, hipStream_t st) {

@@ -25,11 +25,11 @@ namespace lccrf {
 
 constexpr int kTraceBytes = 8192;  // LDS window of pointers walked by each direction of a trace
 
-// Forward chains at 64 < T <= 128 (T % 4 == 0) turn their tiles through LDS like the sum-product
+// Forward chains at 64 < T <= 128 turn their tiles through LDS like the sum-product
 // first pass does (lccrf_chain.hip): a wave then owns 8 complete columns and the maximum over
 // rows never leaves it, so the per-wave candidates below are not needed.
 template <typename G, bool ALIGNED>
-constexpr bool vit_turns() { return G::LPR == 32 && G::WAVES == 16 && G::ITEMS == 4 && ALIGNED; }
+constexpr bool vit_turns() { return G::LPR == 32 && G::WAVES == 16 && G::ITEMS == 4; }
 
 template <typename G, bool TURNED>
 struct VitSmem {
@@ -90,7 +90,7 @@ __global__ __launch_bounds__(G::W) void viterbi_half_kernel(VitArgs a) {
             load_emit4<ALIGNED>(emb + (size_t)i * T, T, c4, v[0]);
             return;
         }
-        load_tile<G, TIN, ALIGNED>(phib + (size_t)i * TT, T, c4, r0, v);
+        load_tile<G, TIN, ALIGNED>(phib + (size_t)i * TT, T, c4, r0, v, b != a.B - 1 || i != N - 1);
     };
     auto tile_ready = [&](float (&v)[ITEMS][4]) {
         if constexpr (CAN_STRUCT) {
@@ -230,7 +230,8 @@ __global__ __launch_bounds__(G::W) void viterbi_half_kernel(VitArgs a) {
             const int first = p0 + 1, n = h - p0;
             if (n > 0) {
                 float ring[PF][4][4];
-                auto load = [&](int i, int slot) { load_tile<G, TIN, true>(phib + (size_t)i * TT, T, c4, r0, ring[slot]); };
+                // (entries outside the matrix hold other entries of it: rows >= T meet -inf, columns >= T are dropped)
+                auto load = [&](int i, int slot) { load_tile<G, TIN, ALIGNED>(phib + (size_t)i * TT, T, c4, r0, ring[slot], b != a.B - 1 || i != N - 1); };
                 auto to_lds = [&](int slot, int wb) {
 #pragma unroll
                     for (int k = 0; k < 4; ++k)
@@ -338,16 +339,17 @@ __global__ __launch_bounds__(1024) void viterbi_stream_kernel(VitArgs a) {
     // unit u = batch u % NBq of the matrix of position first + sdir (u / NBq); addresses clamped into the matrix
     auto load = [&](int u, int slot) {
         const TIN* mat = phib + (size_t)(first + sdir * (u / NBq)) * TT;
+        const bool mat_followed = b != a.B - 1 || first + sdir * (u / NBq) != N - 1;
         const int row0 = kVitBatchRows * (u % NBq) + 4 * wave;
 #pragma unroll
         for (int k = 0; k < 4; ++k) {
             const int s = row0 + k;
-            const TIN* row = mat + (size_t)(s < T ? s : T - 1) * T;
             if (ALIGNED) {
+                const TIN* row = mat + (size_t)(s < T ? s : T - 1) * T;
                 Elem<TIN>::get4_stream(row + (c4 < T ? c4 : T - 4), ring[slot][k]);
-            } else {
-#pragma unroll
-                for (int j = 0; j < 4; ++j) ring[slot][k][j] = Elem<TIN>::get(row + (c4 + j < T ? c4 + j : T - 1));
+            } else {  // (entries outside the matrix hold other entries of it: they meet -inf, or are dropped)
+                if (mat_followed) load_row4_anywhere<TIN, true>(mat, T, s, c4, ring[slot][k]);
+                else load_row4_anywhere<TIN, false>(mat, T, s, c4, ring[slot][k]);
             }
         }
     };
@@ -539,11 +541,16 @@ __device__ __forceinline__ void viterbi_wave_chain(const VitArgs& a, const VitSp
                     else Elem<TIN>::get4(row + c, q);
                     ring[slot][k] = q[0]; ring[slot][k + 1] = q[1]; ring[slot][k + 2] = q[2]; ring[slot][k + 3] = q[3];
                 }
-            } else {
+            } else if constexpr (STRUCT) {
 #pragma unroll
-                for (int k = 0; k < RPL; ++k) {
-                    const int c = c0 + k < T ? c0 + k : T - 1;
-                    ring[slot][k] = STRUCT ? erow[c] : Elem<TIN>::get(row + c);
+                for (int k = 0; k < RPL; ++k) ring[slot][k] = erow[c0 + k < T ? c0 + k : T - 1];
+            } else {  // (entries past the end of the row hold other entries of the matrix: they are masked below)
+#pragma unroll
+                for (int k = 0; k < RPL; k += 4) {
+                    float q[4];
+                    if (sp.b != a.B - 1 || i != a.N - 1) load_row4_anywhere<TIN, true>(phib + (size_t)i * TT, T, sc, c0 + k, q);
+                    else load_row4_anywhere<TIN, false>(phib + (size_t)i * TT, T, sc, c0 + k, q);
+                    ring[slot][k] = q[0]; ring[slot][k + 1] = q[1]; ring[slot][k + 2] = q[2]; ring[slot][k + 3] = q[3];
                 }
             }
         };

@@ -70,19 +70,30 @@ __device__ __forceinline__ void row_to_col(const float (&vr)[WGeo<TP>::R], float
 }
 
 template <int TP, typename TIN, bool ALIGNED>
-__device__ __forceinline__ void wave_load(const TIN* __restrict__ mat, int T, int lane, float (&v)[WGeo<TP>::R][4]) {
+__device__ __forceinline__ void wave_load(const TIN* __restrict__ mat, int T, int lane, float (&v)[WGeo<TP>::R][4],
+                                          bool followed = false) {
     using W = WGeo<TP>;
     const int c4 = 4 * (lane % W::CG), s0 = W::R * (lane / W::CG);
 #pragma unroll
     for (int k = 0; k < W::R; ++k) {
         const int s = s0 + k;
-        const TIN* row = mat + (size_t)(s < T ? s : T - 1) * T;
         if (ALIGNED) {
+            const TIN* row = mat + (size_t)(s < T ? s : T - 1) * T;
             Elem<TIN>::get4(row + (c4 < T ? c4 : T - 4), v[k]);
+        } else if (followed) {  // (the same for the whole wave: a scalar branch)
+            load_row4_anywhere<TIN, true>(mat, T, s, c4, v[k]);
         } else {
-#pragma unroll
-            for (int j = 0; j < 4; ++j) v[k][j] = Elem<TIN>::get(row + (c4 + j < T ? c4 + j : T - 1));
+            load_row4_anywhere<TIN, false>(mat, T, s, c4, v[k]);
         }
+    }
+}
+// What has to follow wave_load where the tile is consumed (nothing if the tag count is a multiple of four).
+template <int TP, bool ALIGNED>
+__device__ __forceinline__ void wave_settle(float (&v)[WGeo<TP>::R][4], int T, int lane) {
+    if constexpr (!ALIGNED) {
+        const int c4 = 4 * (lane % WGeo<TP>::CG);
+#pragma unroll
+        for (int k = 0; k < WGeo<TP>::R; ++k) settle_row4(v[k], T, c4);
     }
 }
 
@@ -347,10 +358,13 @@ __device__ __forceinline__ void wave_half_body(const ChainArgs& a, const Span& s
     constexpr bool structured = STRUCT;
     const float* emb = structured ? a.emit + (size_t)b * N * T : nullptr;
     float tr[R][4];
-    if constexpr (structured) wave_load<TP, float, ALIGNED>(a.trans, T, lane, tr);
+    if constexpr (structured) {
+        wave_load<TP, float, ALIGNED>(a.trans, T, lane, tr);
+        wave_settle<TP, ALIGNED>(tr, T, lane);
+    }
     auto load = [&](int i, int slot) {
         if constexpr (structured) wave_load_emit<TP, ALIGNED>(emb + (size_t)i * T, T, lane, ring[slot]);
-        else wave_load<TP, TIN, ALIGNED>(phib + (size_t)i * TT, T, lane, ring[slot]);
+        else wave_load<TP, TIN, ALIGNED>(phib + (size_t)i * TT, T, lane, ring[slot], b != a.B - 1 || i != N - 1);
     };
     const float none4[4] = {0.f, 0.f, 0.f, 0.f};
     float noneR[R];
@@ -387,6 +401,7 @@ __device__ __forceinline__ void wave_half_body(const ChainArgs& a, const Span& s
         float hc[4] = {0.f, 0.f, 0.f, 0.f};  // entropy of the path behind each tag, column form
         walk<PF>(p0 + 1, h, +1, load, [&](int i, int slot) {
             if constexpr (structured) add_trans<R>(ring[slot], tr);
+            else wave_settle<TP, ALIGNED>(ring[slot], T, lane);
             const float d = settle(i - 1);
             float ua[R], hrow[R];
             col_to_row<TP>(vc, ua, lane);
@@ -430,6 +445,7 @@ __device__ __forceinline__ void wave_half_body(const ChainArgs& a, const Span& s
         for (int k = 0; k < R; ++k) hr[k] = 0.f;
         walk<PF>(e, h + 1, -1, load, [&](int i, int slot) {
             if constexpr (structured) add_trans<R>(ring[slot], tr);
+            else wave_settle<TP, ALIGNED>(ring[slot], T, lane);
             const float d = settle(i);
             float ub[4], hcol[4];
             row_to_col<TP>(vr, ub, lane);
@@ -513,14 +529,17 @@ __device__ __forceinline__ void wave_marginal_body(const ChainArgs& a, const Spa
     static_assert(!(STRUCT && ENT == 2), "no expectations over structured potentials");
     const float* emb = structured ? a.emit + (size_t)b * N * T : nullptr;
     float tr[R][4];
-    if constexpr (structured) wave_load<TP, float, ALIGNED>(a.trans, T, lane, tr);
+    if constexpr (structured) {
+        wave_load<TP, float, ALIGNED>(a.trans, T, lane, tr);
+        wave_settle<TP, ALIGNED>(tr, T, lane);
+    }
     const TIN* psib = ENT == 2 ? static_cast<const TIN*>(a.psi) + (size_t)b * N * TT : nullptr;
     const bool difference = a.ent_kind == 3;
     float ringq[ENT == 2 ? PF : 1][R][4];
     auto load_phi = [&](int i, int slot) {
         if constexpr (structured) wave_load_emit<TP, ALIGNED>(emb + (size_t)i * T, T, lane, ring[slot]);
-        else wave_load<TP, TIN, ALIGNED>(phib + (size_t)i * TT, T, lane, ring[slot]);
-        if constexpr (ENT == 2) wave_load<TP, TIN, ALIGNED>(psib + (size_t)i * TT, T, lane, ringq[slot]);
+        else wave_load<TP, TIN, ALIGNED>(phib + (size_t)i * TT, T, lane, ring[slot], b != a.B - 1 || i != N - 1);
+        if constexpr (ENT == 2) wave_load<TP, TIN, ALIGNED>(psib + (size_t)i * TT, T, lane, ringq[slot], b != a.B - 1 || i != N - 1);
     };
     // the weights of the expectation for the tile in `slot` (before the step rewrites the tile)
     float wt[R][4];
@@ -552,6 +571,8 @@ __device__ __forceinline__ void wave_marginal_body(const ChainArgs& a, const Spa
         };
         walk<PF>(h + 1, e, +1, load, [&](int i, int slot) {
             if constexpr (structured) add_trans<R>(ring[slot], tr);
+            else wave_settle<TP, ALIGNED>(ring[slot], T, lane);
+            if constexpr (ENT == 2) wave_settle<TP, ALIGNED>(ringq[slot], T, lane);
             const float d = finite_or_zero(xor_max<1, W::CG>(max4(vc)));
             kappa += drift_of(tot);
             O += (double)d;
@@ -581,6 +602,8 @@ __device__ __forceinline__ void wave_marginal_body(const ChainArgs& a, const Spa
         };
         walk<PF>(h, p0 + 1, -1, load, [&](int i, int slot) {
             if constexpr (structured) add_trans<R>(ring[slot], tr);
+            else wave_settle<TP, ALIGNED>(ring[slot], T, lane);
+            if constexpr (ENT == 2) wave_settle<TP, ALIGNED>(ringq[slot], T, lane);
             float m = vr[0];
 #pragma unroll
             for (int k = 1; k < R; ++k) m = fmaxf(m, vr[k]);

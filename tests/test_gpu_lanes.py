@@ -2,9 +2,9 @@
 oracle: log-partition and marginals, element by element, on seeded inputs, at the tolerances of
 test_gpu_parity.py (logZ relative 1e-5, marginals absolute 1e-5 / 1e-4 for bfloat16).
 
-The shapes span every block count of the kernels (8 .. 16, 20 .. 32, 36 .. 48, 52 .. 64 tags), tag counts
-that are not a multiple of sixteen (zero padding inside the LDS tiles), chains shorter than the ring of
-tiles, the degenerate lengths 0, 1 and 2, and the inputs that must leave the linear domain: forbidden
+The shapes span every block count of the kernels (8 .. 16, 17 .. 32, 33 .. 48, 52 .. 64 tags), tag counts
+that are not a multiple of sixteen (zero padding inside the LDS tiles) or of four (matrices loaded element by
+element, the last piece of a row cut short), chains shorter than the ring of tiles, the degenerate lengths 0, 1 and 2, and the inputs that must leave the linear domain: forbidden
 edges (-inf), sequences with no finite path, scales that jump by hundreds of nats between positions and a
 large common offset.
 """
@@ -17,7 +17,7 @@ from test_gpu_parity import check_case, crf  # noqa: F401  (crf: the module-scop
 
 pytestmark = pytest.mark.gpu
 
-TAGS = (8, 12, 16, 20, 32, 40, 48, 52, 64)
+TAGS = (8, 9, 10, 11, 12, 13, 16, 17, 20, 21, 30, 32, 33, 40, 45, 47, 48, 52, 64)
 
 
 @pytest.mark.parametrize("T", TAGS)
@@ -30,7 +30,7 @@ def test_lanes_sweep_fp32(crf, oracle_mod, T, N):
                queries=("logz", "mu"))
 
 
-@pytest.mark.parametrize("T,N", [(16, 70), (32, 41), (48, 33), (64, 25), (24, 9)])
+@pytest.mark.parametrize("T,N", [(16, 70), (32, 41), (48, 33), (64, 25), (24, 9), (9, 50), (27, 40), (45, 33)])
 def test_lanes_sweep_bf16(crf, oracle_mod, T, N):
     phi, _ = workloads.random_case(9100 + T + N, 3, N, T, scale=3.0, dtype="bf16")
     lens = torch.tensor([N, max(1, N // 3), N - 1 if N > 1 else 1], dtype=torch.int32)
@@ -44,7 +44,7 @@ def test_lanes_no_lengths_argument(crf, oracle_mod):
                queries=("logz", "mu"))
 
 
-@pytest.mark.parametrize("T", (16, 32, 48, 64))
+@pytest.mark.parametrize("T", (13, 16, 29, 32, 45, 48, 64))
 def test_lanes_forbidden_edges_take_the_log_domain_tail(crf, oracle_mod, T):
     N = 24
     phi, _ = workloads.random_case(9300 + T, 5, N, T)
@@ -62,7 +62,7 @@ def test_lanes_forbidden_edges_take_the_log_domain_tail(crf, oracle_mod, T):
                what=f"lanes -inf T={T}", queries=("logz", "mu"))
 
 
-@pytest.mark.parametrize("T,N", [(16, 64), (32, 40), (36, 44), (48, 21), (60, 25), (64, 30)])
+@pytest.mark.parametrize("T,N", [(16, 64), (30, 40), (32, 40), (36, 44), (45, 30), (48, 21), (60, 25), (64, 30)])
 def test_lanes_scale_jumps(crf, oracle_mod, T, N):
     """A common shift of a whole matrix is absorbed by the matrix's own power-of-two scale: the chain stays
     in the linear domain and the offsets carry the jumps."""
@@ -75,7 +75,7 @@ def test_lanes_scale_jumps(crf, oracle_mod, T, N):
                queries=("logz", "mu"))
 
 
-@pytest.mark.parametrize("T", (16, 48))
+@pytest.mark.parametrize("T", (16, 45, 48))
 def test_lanes_wide_range_inside_a_matrix(crf, oracle_mod, T):
     """Entries of one matrix hundreds of nats apart: sums fall below the accepted range somewhere in the
     chain; those positions are taken in the log domain by the chain wave, and the fast path resumes once the
@@ -114,7 +114,7 @@ def test_lanes_chain_that_stops_waiting_finishes_in_the_log_domain(crf, oracle_m
     (wherever a producer happens to be late); every result still equals the oracle's, and every kernel ends."""
     crf.set_lane_poll_limit(polls)
     try:
-        for T, N in ((16, 50), (32, 70), (48, 40), (64, 33)):
+        for T, N in ((11, 60), (16, 50), (32, 70), (45, 40), (48, 40), (64, 33)):
             phi, lens = workloads.random_case(9800 + T + polls, 5, N, T, scale=1.5, ragged=True, min_len=1)
             check_case(crf, oracle_mod, phi, lens, algo=crf.ALGO_SEQUENTIAL_LANES,
                        what=f"lanes poll limit {polls} T={T}", queries=("logz", "mu"))
@@ -130,7 +130,7 @@ def test_lanes_more_sequences_than_compute_units(crf, oracle_mod):
 
 def test_lanes_refuses_what_it_does_not_serve(crf):
     dev = torch.device("cuda:0")
-    for T in (5, 18, 68, 128):
+    for T in (5, 49, 50, 63, 68, 128):
         phi = torch.zeros(1, 4, T, T, device=dev)
         with pytest.raises(RuntimeError):
             crf.lccrf_log_partition(phi, algo=crf.ALGO_SEQUENTIAL_LANES)

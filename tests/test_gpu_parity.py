@@ -137,6 +137,45 @@ def test_sweep_bf16(crf, oracle_mod, T, N):
     check_case(crf, oracle_mod, phi, lens, poison=False, what=f"bf16 T={T} N={N}")
 
 
+@pytest.mark.parametrize("T", (6, 7, 9, 13, 21, 30, 33, 45, 50, 63, 75, 99, 127))
+@pytest.mark.parametrize("N", (2, 9, 40))
+def test_sweep_tag_counts_off_the_16_byte_grid(crf, oracle_mod, T, N):
+    """Tag counts that are no multiple of four under the sequential schedule: the rows of a matrix then lie at any
+    multiple of four bytes (two for bfloat16), a piece of four columns is loaded from wherever it starts, the pieces
+    that run past the end of a row take what follows in the matrix, and the piece that ends a matrix is loaded
+    element by element (the poisoned positions behind a sequence's last matrix must stay unread).  Speculative and
+    exact step, all three queries; bfloat16 for the chains long enough to have a middle."""
+    B = 4
+    phi, _ = workloads.random_case(2500 + 11 * T + N, B, N, T, scale=1.5)
+    lens = torch.tensor([N, 1, max(1, N // 2), max(1, N - 1)], dtype=torch.int32)
+    check_case(crf, oracle_mod, phi, lens, algo=crf.ALGO_SEQUENTIAL, what=f"sequential T={T} N={N}")
+    check_case(crf, oracle_mod, phi, lens, algo=crf.ALGO_SEQUENTIAL_EXACT, what=f"exact T={T} N={N}", queries=("logz", "mu"))
+    if N == 40:
+        phi, _ = workloads.random_case(2600 + T, 2, N, T, scale=4.0, dtype="bf16")
+        check_case(crf, oracle_mod, phi, torch.tensor([N, N - 3], dtype=torch.int32), poison=False,
+                   algo=crf.ALGO_SEQUENTIAL, what=f"sequential bf16 T={T}")
+
+
+@pytest.mark.parametrize("T", (13, 30, 45, 63, 99))
+def test_tag_counts_off_the_16_byte_grid_forbidden_edges_and_jumps(crf, oracle_mod, T):
+    """The same tag counts with -inf potentials, a sequence without a finite path and scales that jump by hundreds
+    of nats between positions (rejected speculative steps, replayed exactly)."""
+    N = 24
+    phi, _ = workloads.random_case(2700 + T, 5, N, T)
+    ninf = float("-inf")
+    phi[0, 5, :, 7] = ninf
+    phi[0, 19, 3, :] = ninf
+    phi[1, 8, :, :] = ninf
+    phi[2, 0, 0, 2] = ninf
+    phi[3, 12, :, 1:] = ninf
+    phi[3, 12, :, T - 1] = 0.0              # (the last column of a row: the piece that is cut short)
+    phi[3, 12, :, 0] = ninf
+    phi[4, ::3] += 300.0
+    phi[4, 1::3] -= 300.0
+    lens = torch.tensor([N, N, N, N, N - 3], dtype=torch.int32)
+    check_case(crf, oracle_mod, phi, lens, poison=False, algo=crf.ALGO_SEQUENTIAL, what=f"sequential -inf / jumps T={T}")
+
+
 @pytest.mark.parametrize("T", [255, 256, 129, 200])
 def test_largest_tag_sets(crf, oracle_mod, T):
     phi, _ = workloads.random_case(3000 + T, 2, 5, T)

@@ -93,18 +93,31 @@ def test_structured_agrees_with_dense_call(crf):
     assert torch.equal(y_a, y_b) and torch.equal(s_a, s_b)
 
 
-@pytest.mark.parametrize("T", (20, 24, 32, 40, 48))
+@pytest.mark.parametrize("T", (17, 20, 21, 24, 30, 32, 40, 45, 48))
 @pytest.mark.parametrize("N", (2, 7, 45))
 def test_structured_on_the_chain_wave_kernels(crf, oracle_mod, T, N):
-    """17 .. 48 tags in multiples of four, batches that leave the chip latency-bound: the sum queries take the
-    chain-wave / producer-wave kernels, whose producers form trans + emit in registers."""
+    """8 .. 48 tags, batches that leave the chip latency-bound: the sum queries take the chain-wave / producer-wave
+    kernels, whose producers form trans + emit in registers (tag counts that are no multiple of four element by
+    element)."""
     assert crf.auto_algo(crf.OP_MARGINALS, 6, N, T) == crf.ALGO_SEQUENTIAL_LANES
     emit, trans = _make(7250 + 3 * T + N, 6, N, T)
     lens = torch.tensor([N, 1, max(1, N // 2), 0, max(1, N - 1), min(N, 2)], dtype=torch.int32)
     _check(crf, oracle_mod, emit, trans, lens, f"structured lanes T={T} N={N}")
 
 
-@pytest.mark.parametrize("T", (32, 48))
+@pytest.mark.parametrize("T", (8, 9, 13, 16))
+def test_structured_on_the_chain_wave_kernels_up_to_16_tags(crf, oracle_mod, T):
+    """8 .. 16 tags take the chain-wave kernels for chains of 16 positions or more in batches of at most one sequence
+    a compute unit (shorter chains do not pay their start)."""
+    B, N = 6, 45
+    assert crf.auto_algo(crf.OP_MARGINALS, B, N, T) == crf.ALGO_SEQUENTIAL_LANES
+    assert crf.auto_algo(crf.OP_MARGINALS, B, 12, T) == crf.ALGO_SEQUENTIAL
+    emit, trans = _make(7255 + T, B, N, T)
+    lens = torch.tensor([N, 1, N // 2, 0, N - 1, 2], dtype=torch.int32)
+    _check(crf, oracle_mod, emit, trans, lens, f"structured lanes T={T} N={N}")
+
+
+@pytest.mark.parametrize("T", (32, 45, 48))
 def test_structured_chain_wave_kernels_leave_the_linear_domain(crf, oracle_mod, T):
     """Forbidden transitions and peaked emissions: positions the scaled single-precision step rejects are taken in
     the log domain by the chain wave, from trans + emit as well; and with the wait for a matrix made to expire from
@@ -125,9 +138,9 @@ def test_structured_chain_wave_kernels_leave_the_linear_domain(crf, oracle_mod, 
         crf.set_lane_poll_limit(-1)
 
 
-@pytest.mark.parametrize("T", (8, 16, 32, 48))
+@pytest.mark.parametrize("T", (8, 13, 16, 32, 45, 48))
 def test_structured_argmax_on_the_chain_wave_kernels(crf, oracle_mod, T):
-    """Up to 48 tags in multiples of four the structured argmax takes the max-plus chain-wave kernels where the dense
+    """Up to 48 tags the structured argmax takes the max-plus chain-wave kernels where the dense
     one does (their helpers form trans + emit in registers): tags and scores of the dense call bit for bit, exact
     ties (integer scores) and forbidden transitions included; and with the wait for a matrix made to expire."""
     B, N = 6, 70
