@@ -45,18 +45,29 @@ struct BatchSlot {
 };
 
 // This thread's part of rows row0 .. row0 + 3 of one matrix, addresses clamped into the matrix.
+// (A tag count that is no multiple of four: see load_row4_anywhere; `followed`: another matrix of the tensor lies
+// behind this one, the same for the whole workgroup.  settle_batch() has to come before the values are used.)
 template <typename TIN, bool ALIGNED>
-__device__ __forceinline__ void load_batch(const TIN* __restrict__ mat, int T, int row0, int c4, float (&v)[4][4]) {
+__device__ __forceinline__ void load_batch(const TIN* __restrict__ mat, int T, int row0, int c4, float (&v)[4][4],
+                                           bool followed = false) {
 #pragma unroll
     for (int k = 0; k < 4; ++k) {
         const int s = row0 + k;
-        const TIN* row = mat + (size_t)(s < T ? s : T - 1) * T;
         if (ALIGNED) {
+            const TIN* row = mat + (size_t)(s < T ? s : T - 1) * T;
             Elem<TIN>::get4_stream(row + (c4 < T ? c4 : T - 4), v[k]);
+        } else if (followed) {
+            load_row4_anywhere<TIN, true>(mat, T, s, c4, v[k]);
         } else {
-#pragma unroll
-            for (int j = 0; j < 4; ++j) v[k][j] = Elem<TIN>::get(row + (c4 + j < T ? c4 + j : T - 1));
+            load_row4_anywhere<TIN, false>(mat, T, s, c4, v[k]);
         }
+    }
+}
+template <bool ALIGNED>
+__device__ __forceinline__ void settle_batch(float (&v)[4][4], int T, int c4) {
+    if constexpr (!ALIGNED) {
+#pragma unroll
+        for (int k = 0; k < 4; ++k) settle_row4(v[k], T, c4);
     }
 }
 
@@ -161,7 +172,7 @@ __global__ __launch_bounds__(1024) void stream_chain_kernel(ChainArgs a) {
     // neither holds a branch around its loads
     auto load_forward = [&](int u, int slot) {
         const int pos = first + u / NBq, q = u % NBq;
-        load_batch<TIN, ALIGNED>(phib + (size_t)pos * TT, T, kBatchRows * q + 4 * wave, c4, ring[slot].v);
+        load_batch<TIN, ALIGNED>(phib + (size_t)pos * TT, T, kBatchRows * q + 4 * wave, c4, ring[slot].v, b != a.B - 1 || pos != N - 1);
         if constexpr (WITH_MU) {
             load_vec4<ALIGNED>(a.ub + (vb + pos) * T, T, c4, ring[slot].ax);
             ring[slot].o = a.Ob[vb + pos];
@@ -170,7 +181,7 @@ __global__ __launch_bounds__(1024) void stream_chain_kernel(ChainArgs a) {
     auto load_backward = [&](int u, int slot) {
         const int pos = first - u / NBq, q = u % NBq;
         const int row0 = kBatchRows * q + 4 * wave;
-        load_batch<TIN, ALIGNED>(phib + (size_t)pos * TT, T, row0, c4, ring[slot].v);
+        load_batch<TIN, ALIGNED>(phib + (size_t)pos * TT, T, row0, c4, ring[slot].v, b != a.B - 1 || pos != N - 1);
         if constexpr (WITH_MU) {
             load_vec4<ALIGNED>(a.ua + (vb + pos - 1) * T, T, row0, ring[slot].ax);
             ring[slot].o = a.Oa[vb + pos - 1];
@@ -184,7 +195,8 @@ __global__ __launch_bounds__(1024) void stream_chain_kernel(ChainArgs a) {
         for (int q = 0; q < NBq; ++q) {
             const int row0 = kBatchRows * q + 4 * wave;
             float v[4][4];
-            load_batch<TIN, ALIGNED>(mat, T, row0, c4, v);
+            load_batch<TIN, ALIGNED>(mat, T, row0, c4, v, b != a.B - 1 || i != N - 1);
+            settle_batch<ALIGNED>(v, T, c4);
             const float4 r4 = *reinterpret_cast<const float4*>(&sm.rvec[buf][row0]);
             const float ua[4] = {r4.x - d, r4.y - d, r4.z - d, r4.w - d};  // -inf for rows >= T
 #pragma unroll
@@ -202,7 +214,8 @@ __global__ __launch_bounds__(1024) void stream_chain_kernel(ChainArgs a) {
         for (int q = 0; q < NBq; ++q) {
             const int row0 = kBatchRows * q + 4 * wave;
             float v[4][4];
-            load_batch<TIN, ALIGNED>(mat, T, row0, c4, v);
+            load_batch<TIN, ALIGNED>(mat, T, row0, c4, v, b != a.B - 1 || i != N - 1);
+            settle_batch<ALIGNED>(v, T, c4);
             const float4 r4 = *reinterpret_cast<const float4*>(&sm.rvec[buf][row0]);
             const float ua[4] = {r4.x - d, r4.y - d, r4.z - d, r4.w - d};
 #pragma unroll
@@ -251,7 +264,8 @@ __global__ __launch_bounds__(1024) void stream_chain_kernel(ChainArgs a) {
         for (int q = 0; q < NBq; ++q) {
             const int row0 = kBatchRows * q + 4 * wave;
             float v[4][4], uaK[4] = {0.f, 0.f, 0.f, 0.f};
-            load_batch<TIN, ALIGNED>(mat, T, row0, c4, v);
+            load_batch<TIN, ALIGNED>(mat, T, row0, c4, v, b != a.B - 1 || i != N - 1);
+            settle_batch<ALIGNED>(v, T, c4);
             if constexpr (WITH_MU) {
                 float ax[4];
                 load_vec4<ALIGNED>(a.ua + (vb + i - 1) * T, T, row0, ax);
@@ -291,6 +305,7 @@ __global__ __launch_bounds__(1024) void stream_chain_kernel(ChainArgs a) {
     if (dir == 0) {
         // ---------------- forward chain ----------------
         walk<kStreamRing<WITH_MU>>(0, n * NBq - 1, +1, load_forward, [&](int u, int slot) {
+            settle_batch<ALIGNED>(ring[slot].v, T, c4);
             const int i = first + u / NBq, q = u % NBq;
             const int row0 = kBatchRows * q + 4 * wave;
             if (q == 0) {
@@ -364,6 +379,7 @@ __global__ __launch_bounds__(1024) void stream_chain_kernel(ChainArgs a) {
     } else {
         // ---------------- backward chain ----------------
         walk<kStreamRing<WITH_MU>>(0, n * NBq - 1, +1, load_backward, [&](int u, int slot) {
+            settle_batch<ALIGNED>(ring[slot].v, T, c4);
             const int i = first - u / NBq, q = u % NBq;
             const int row0 = kBatchRows * q + 4 * wave;
             if (q == 0) {
@@ -520,8 +536,8 @@ __global__ __launch_bounds__(1024) void stream_expect_kernel(ChainArgs a) {
     float qring[CROSS ? RING : 1][4][4];
     auto load = [&](int u, int slot) {
         const int pos = dir == 0 ? first + u / NBq : first - u / NBq, q = u % NBq;
-        load_batch<TIN, ALIGNED>(phib + (size_t)pos * TT, T, kBatchRows * q + 4 * wave, c4, ring[slot]);
-        if constexpr (CROSS) load_batch<TIN, ALIGNED>(psib + (size_t)pos * TT, T, kBatchRows * q + 4 * wave, c4, qring[slot]);
+        load_batch<TIN, ALIGNED>(phib + (size_t)pos * TT, T, kBatchRows * q + 4 * wave, c4, ring[slot], b != a.B - 1 || pos != N - 1);
+        if constexpr (CROSS) load_batch<TIN, ALIGNED>(psib + (size_t)pos * TT, T, kBatchRows * q + 4 * wave, c4, qring[slot], b != a.B - 1 || pos != N - 1);
     };
     // publishes the column threads' results of a forward step (r, hv: this thread's column, or -inf / 0)
     auto publish_forward = [&](float r, float hv) {
@@ -542,7 +558,8 @@ __global__ __launch_bounds__(1024) void stream_expect_kernel(ChainArgs a) {
         for (int q = 0; q < NBq; ++q) {
             const int row0 = kBatchRows * q + 4 * wave;
             float v[4][4];
-            load_batch<TIN, ALIGNED>(mat, T, row0, c4, v);
+            load_batch<TIN, ALIGNED>(mat, T, row0, c4, v, b != a.B - 1 || i != N - 1);
+            settle_batch<ALIGNED>(v, T, c4);
             const float4 r4 = *reinterpret_cast<const float4*>(&sm.rvec[buf][row0]);
             const float ua[4] = {r4.x - d, r4.y - d, r4.z - d, r4.w - d};  // -inf for rows >= T
 #pragma unroll
@@ -563,8 +580,12 @@ __global__ __launch_bounds__(1024) void stream_expect_kernel(ChainArgs a) {
         for (int q = 0; q < NBq; ++q) {
             const int row0 = kBatchRows * q + 4 * wave;
             float v[4][4], qv[4][4];
-            load_batch<TIN, ALIGNED>(mat, T, row0, c4, v);
-            if constexpr (CROSS) load_batch<TIN, ALIGNED>(qmat, T, row0, c4, qv);
+            load_batch<TIN, ALIGNED>(mat, T, row0, c4, v, b != a.B - 1 || i != N - 1);
+            settle_batch<ALIGNED>(v, T, c4);
+            if constexpr (CROSS) {
+                load_batch<TIN, ALIGNED>(qmat, T, row0, c4, qv, b != a.B - 1 || i != N - 1);
+                settle_batch<ALIGNED>(qv, T, c4);
+            }
             const float4 r4 = *reinterpret_cast<const float4*>(&sm.rvec[buf][row0]);
             const float4 h4 = *reinterpret_cast<const float4*>(&hvec[buf][row0]);
             const float ua[4] = {r4.x - d, r4.y - d, r4.z - d, r4.w - d};
@@ -609,8 +630,12 @@ __global__ __launch_bounds__(1024) void stream_expect_kernel(ChainArgs a) {
         for (int q = 0; q < NBq; ++q) {
             const int row0 = kBatchRows * q + 4 * wave;
             float v[4][4], qv[4][4];
-            load_batch<TIN, ALIGNED>(mat, T, row0, c4, v);
-            if constexpr (CROSS) load_batch<TIN, ALIGNED>(qmat, T, row0, c4, qv);
+            load_batch<TIN, ALIGNED>(mat, T, row0, c4, v, b != a.B - 1 || i != N - 1);
+            settle_batch<ALIGNED>(v, T, c4);
+            if constexpr (CROSS) {
+                load_batch<TIN, ALIGNED>(qmat, T, row0, c4, qv, b != a.B - 1 || i != N - 1);
+                settle_batch<ALIGNED>(qv, T, c4);
+            }
 #pragma unroll
             for (int k = 0; k < 4; ++k) {
                 float y[4];
@@ -648,6 +673,8 @@ __global__ __launch_bounds__(1024) void stream_expect_kernel(ChainArgs a) {
 
     if (dir == 0) {
         walk<RING>(0, n * NBq - 1, +1, load, [&](int u, int slot) {
+            settle_batch<ALIGNED>(ring[slot], T, c4);
+            if constexpr (CROSS) settle_batch<ALIGNED>(qring[slot], T, c4);
             const int i = first + u / NBq, q = u % NBq;
             const int row0 = kBatchRows * q + 4 * wave;
             if (q == 0) {
@@ -705,6 +732,8 @@ __global__ __launch_bounds__(1024) void stream_expect_kernel(ChainArgs a) {
         });
     } else {
         walk<RING>(0, n * NBq - 1, +1, load, [&](int u, int slot) {
+            settle_batch<ALIGNED>(ring[slot], T, c4);
+            if constexpr (CROSS) settle_batch<ALIGNED>(qring[slot], T, c4);
             const int i = first - u / NBq, q = u % NBq;
             const int row0 = kBatchRows * q + 4 * wave;
             if (q == 0) {
