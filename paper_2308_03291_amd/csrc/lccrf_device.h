@@ -493,10 +493,11 @@ __device__ __forceinline__ void store4(float* __restrict__ mu_out, int T, int s,
             else *reinterpret_cast<float4*>(p) = make_float4(a0, a1, a2, a3);
         } else if (c4 + 4 <= T) {
             store4_anywhere(p, a0, a1, a2, a3);
-        } else {
+        } else {  // the piece that ends the row holds T % 4 columns: the same count in every thread that gets here
+            const int nv = T & 3;
             p[0] = a0;
-            if (c4 + 1 < T) p[1] = a1;
-            if (c4 + 2 < T) p[2] = a2;
+            if (nv > 1) p[1] = a1;
+            if (nv > 2) p[2] = a2;
         }
     }
 }
