@@ -6,7 +6,8 @@
 // four consecutive columns (t = 4c .. 4c+3, c = tid % LPR); the W / LPR row groups cover
 // rows r0, r0 + RPP, r0 + 2 RPP, ... (r0 = tid / LPR, RPP = W / LPR), ITEMS rows per
 // thread.  A wave therefore reads whole, contiguous rows: every global load is coalesced,
-// and 16-byte wide whenever T is a multiple of 4.
+// and 16 bytes wide: aligned when T is a multiple of 4, from wherever the piece starts otherwise
+// (load_row4_anywhere).
 //
 //   reduction over s (forward recursion): in-thread over ITEMS rows, then across the
 //       64 / LPR row groups of a wave by lane exchange, then across waves through LDS;

@@ -84,12 +84,14 @@ __global__ __launch_bounds__(64 * WAVES) void semi_forward_kernel(SemiArgs a) {
         for (int m = 0; m < ITEMS; ++m) {
             const int p = ITEMS * lbt + m;
             const int k = (p / PPT) * TPP + k0, s = r0 + (p % PPT) * RPP;
-            const TIN* row = mat + (size_t)(k < K ? k : K - 1) * TT + (size_t)(s < T ? s : T - 1) * T;
+            const TIN* matk = mat + (size_t)(k < K ? k : K - 1) * TT;
             if (ALIGNED) {
+                const TIN* row = matk + (size_t)(s < T ? s : T - 1) * T;
                 Elem<TIN>::get4(row + (c4 < T ? c4 : T - 4), tile[slot][m]);
+            } else if (b != a.B - 1 || li != N - 1) {  // (matrices of a later position lie behind these)
+                load_row4_anywhere<TIN, true>(matk, T, s, c4, tile[slot][m]);
             } else {
-#pragma unroll
-                for (int j = 0; j < 4; ++j) tile[slot][m][j] = Elem<TIN>::get(row + (c4 + j < T ? c4 + j : T - 1));
+                load_row4_anywhere<TIN, false>(matk, T, s, c4, tile[slot][m]);
             }
         }
         if (q < total - 1 && ++lbt == nb) {
@@ -137,6 +139,7 @@ __global__ __launch_bounds__(64 * WAVES) void semi_forward_kernel(SemiArgs a) {
             float rv = ring[sl * T + (s < T ? s : T - 1)];
             asm volatile("" : "+v"(rv));
             const float v = rv + (float)(base[sl] - R);
+            if constexpr (!ALIGNED) settle_row4(tile[slot][m], T, c4);
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
                 x[m][j] = row_ok ? __builtin_fmaf(tile[slot][m][j], kLog2e, v) : LCCRF_NEG_INF;
