@@ -113,7 +113,8 @@ struct Geo {
 // four elements come as one load wherever four elements follow in the matrix: those past the end of the row are then
 // the first of the next row.  Only the piece that ends the matrix (the last columns of the last row) is loaded element
 // by element, and that only if nothing follows the matrix in memory (FOLLOWED says that something does: another
-// matrix of the tensor; then the load is the same instruction in every thread, with no branch around it).
+// matrix of the tensor, of two tags or more, so that the three elements a load may run over are there; then the
+// load is the same instruction in every thread, with no branch around it).
 // settle_row4() makes of what was loaded the piece every consumer may rely on; nothing here touches the loaded
 // values, so the loads stay in flight.
 template <typename TIN, bool FOLLOWED>
@@ -150,7 +151,7 @@ __device__ __forceinline__ void load_tile(const TIN* __restrict__ mat, int T, in
             const TIN* row = mat + (size_t)(s < T ? s : T - 1) * T;
             if (G::TCAP > 64) Elem<TIN>::get4_stream(row + (c4 < T ? c4 : T - 4), v[k]);  // T % 4 == 0 here, so T >= 4
             else Elem<TIN>::get4(row + (c4 < T ? c4 : T - 4), v[k]);
-        } else if (followed) {  // (the same for the whole workgroup: a scalar branch)
+        } else if (followed && T > 1) {  // (the same for the whole workgroup: a scalar branch)
             load_row4_anywhere<TIN, true>(mat, T, s, c4, v[k]);
         } else {
             load_row4_anywhere<TIN, false>(mat, T, s, c4, v[k]);

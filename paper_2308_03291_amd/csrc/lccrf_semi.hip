@@ -88,7 +88,7 @@ __global__ __launch_bounds__(64 * WAVES) void semi_forward_kernel(SemiArgs a) {
             if (ALIGNED) {
                 const TIN* row = matk + (size_t)(s < T ? s : T - 1) * T;
                 Elem<TIN>::get4(row + (c4 < T ? c4 : T - 4), tile[slot][m]);
-            } else if (b != a.B - 1 || li != N - 1) {  // (matrices of a later position lie behind these)
+            } else if ((b != a.B - 1 || li != N - 1) && T > 1) {  // (matrices of a later position lie behind these)
                 load_row4_anywhere<TIN, true>(matk, T, s, c4, tile[slot][m]);
             } else {
                 load_row4_anywhere<TIN, false>(matk, T, s, c4, tile[slot][m]);

@@ -56,7 +56,7 @@ __device__ __forceinline__ void load_batch(const TIN* __restrict__ mat, int T, i
         if (ALIGNED) {
             const TIN* row = mat + (size_t)(s < T ? s : T - 1) * T;
             Elem<TIN>::get4_stream(row + (c4 < T ? c4 : T - 4), v[k]);
-        } else if (followed) {
+        } else if (followed && T > 1) {
             load_row4_anywhere<TIN, true>(mat, T, s, c4, v[k]);
         } else {
             load_row4_anywhere<TIN, false>(mat, T, s, c4, v[k]);

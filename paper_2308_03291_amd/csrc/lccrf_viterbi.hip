@@ -348,7 +348,7 @@ __global__ __launch_bounds__(1024) void viterbi_stream_kernel(VitArgs a) {
                 const TIN* row = mat + (size_t)(s < T ? s : T - 1) * T;
                 Elem<TIN>::get4_stream(row + (c4 < T ? c4 : T - 4), ring[slot][k]);
             } else {  // (entries outside the matrix hold other entries of it: they meet -inf, or are dropped)
-                if (mat_followed) load_row4_anywhere<TIN, true>(mat, T, s, c4, ring[slot][k]);
+                if (mat_followed && T > 1) load_row4_anywhere<TIN, true>(mat, T, s, c4, ring[slot][k]);
                 else load_row4_anywhere<TIN, false>(mat, T, s, c4, ring[slot][k]);
             }
         }
@@ -548,7 +548,7 @@ __device__ __forceinline__ void viterbi_wave_chain(const VitArgs& a, const VitSp
 #pragma unroll
                 for (int k = 0; k < RPL; k += 4) {
                     float q[4];
-                    if (sp.b != a.B - 1 || i != a.N - 1) load_row4_anywhere<TIN, true>(phib + (size_t)i * TT, T, sc, c0 + k, q);
+                    if ((sp.b != a.B - 1 || i != a.N - 1) && T > 1) load_row4_anywhere<TIN, true>(phib + (size_t)i * TT, T, sc, c0 + k, q);
                     else load_row4_anywhere<TIN, false>(phib + (size_t)i * TT, T, sc, c0 + k, q);
                     ring[slot][k] = q[0]; ring[slot][k + 1] = q[1]; ring[slot][k + 2] = q[2]; ring[slot][k + 3] = q[3];
                 }

@@ -80,7 +80,7 @@ __device__ __forceinline__ void wave_load(const TIN* __restrict__ mat, int T, in
         if (ALIGNED) {
             const TIN* row = mat + (size_t)(s < T ? s : T - 1) * T;
             Elem<TIN>::get4(row + (c4 < T ? c4 : T - 4), v[k]);
-        } else if (followed) {  // (the same for the whole wave: a scalar branch)
+        } else if (followed && T > 1) {  // (the same for the whole wave: a scalar branch)
             load_row4_anywhere<TIN, true>(mat, T, s, c4, v[k]);
         } else {
             load_row4_anywhere<TIN, false>(mat, T, s, c4, v[k]);

@@ -176,6 +176,25 @@ def test_tag_counts_off_the_16_byte_grid_forbidden_edges_and_jumps(crf, oracle_m
     check_case(crf, oracle_mod, phi, lens, poison=False, algo=crf.ALGO_SEQUENTIAL, what=f"sequential -inf / jumps T={T}")
 
 
+@pytest.mark.parametrize("T", (1, 2, 3, 5, 7, 13, 30, 45, 99, 131, 255))
+def test_the_last_matrix_of_the_tensor_with_nothing_usable_behind_it(crf, oracle_mod, T):
+    """Full-length sequences, so that the last matrix of the tensor is worked on, in a buffer that holds NaN right
+    behind (and before) the tensor: whatever a load of four columns takes in past the end of a row must not reach a
+    result, and for the piece that ends the tensor nothing past it is loaded at all (that part cannot be seen from
+    the results; the kernels take the element-wise path there)."""
+    B, N = 2, 3
+    phi, _ = workloads.random_case(2800 + T, B, N, T, scale=1.5)
+    n = phi.numel()
+    buf = torch.full((n + 64,), float("nan"), device="cuda:0")
+    buf[32:32 + n] = phi.reshape(-1).to("cuda:0")          # (32 floats in: the tensor stays 16-byte aligned)
+    dphi = buf[32:32 + n].view(B, N, T, T)
+    for algo in (crf.ALGO_SEQUENTIAL, crf.ALGO_SEQUENTIAL_EXACT):
+        check_case(crf, oracle_mod, phi, None, algo=algo, what=f"tensor end T={T} algo={algo}", device_phi=dphi,
+                   queries=("logz", "mu") if algo == crf.ALGO_SEQUENTIAL_EXACT else ("logz", "mu", "vit"))
+    if 8 <= T <= 48:
+        check_case(crf, oracle_mod, phi, None, algo=crf.ALGO_SEQUENTIAL_LANES, what=f"tensor end, lanes T={T}", device_phi=dphi)
+
+
 @pytest.mark.parametrize("T", [255, 256, 129, 200])
 def test_largest_tag_sets(crf, oracle_mod, T):
     phi, _ = workloads.random_case(3000 + T, 2, 5, T)
