@@ -252,9 +252,9 @@ inline bool lanes_pay_sum(int op, int B, int N, int T) {
 // argmax, sequential / these (us): B=256 N=256 T=16 71 / 45, B=512 N=256 T=16 79 / 62, B=1024 N=64 T=16 33 / 38;
 // B=128 N=256 T=32 106 / 59, B=256 N=128 T=32 64 / 57, B=384 N=128 T=32 68 / 75; B=128 N=128 T=48 99 / 74,
 // B=64 N=256 T=40 181 / 117, B=256 N=128 T=48 127 / 130; above 48 tags the ring holds too few matrices
-// (B=32 N=256 T=64 182 / 208).  Tag counts that are no multiple of four load their matrices element by element and
-// gain less (B=128 N=128 T=45 128 / 86, T=48 99 / 74; B=32 N=64 T=30 38 / 28); chains of fewer than 16 positions do
-// not pay the kernel's start (B=4 N=8 T=5 17.8 / 18.6).
+// (B=32 N=256 T=64 182 / 208).  Tag counts that are no multiple of four gain the same (B=128 N=128 T=45 106 / 76,
+// T=48 96 / 72; B=32 N=64 T=30 43 / 27); chains of fewer than 16 positions do not pay the kernel's start
+// (B=4 N=8 T=5 17.8 / 18.6).
 inline bool lanes_pay_max(int B, int N, int T) {
     if (!lccrf::lane_max_supported(T) || T > 48 || N < 16) return false;
     const int cus = current_device_cus();

@@ -144,18 +144,20 @@ __device__ __forceinline__ void settle_row4(float (&o)[4], int T, int c4) {
 template <typename G, typename TIN, bool ALIGNED>
 __device__ __forceinline__ void load_tile(const TIN* __restrict__ mat, int T, int c4, int r0,
                                           float (&v)[G::ITEMS][4], bool followed = false) {
+    if (ALIGNED) {
 #pragma unroll
-    for (int k = 0; k < G::ITEMS; ++k) {
-        const int s = r0 + k * G::RPP;
-        if (ALIGNED) {
+        for (int k = 0; k < G::ITEMS; ++k) {
+            const int s = r0 + k * G::RPP;
             const TIN* row = mat + (size_t)(s < T ? s : T - 1) * T;
             if (G::TCAP > 64) Elem<TIN>::get4_stream(row + (c4 < T ? c4 : T - 4), v[k]);  // T % 4 == 0 here, so T >= 4
             else Elem<TIN>::get4(row + (c4 < T ? c4 : T - 4), v[k]);
-        } else if (followed && T > 1) {  // (the same for the whole workgroup: a scalar branch)
-            load_row4_anywhere<TIN, true>(mat, T, s, c4, v[k]);
-        } else {
-            load_row4_anywhere<TIN, false>(mat, T, s, c4, v[k]);
         }
+    } else if (followed && T > 1) {  // (the same for the whole workgroup: one scalar branch)
+#pragma unroll
+        for (int k = 0; k < G::ITEMS; ++k) load_row4_anywhere<TIN, true>(mat, T, r0 + k * G::RPP, c4, v[k]);
+    } else {
+#pragma unroll
+        for (int k = 0; k < G::ITEMS; ++k) load_row4_anywhere<TIN, false>(mat, T, r0 + k * G::RPP, c4, v[k]);
     }
 }
 template <typename G, bool ALIGNED>

@@ -84,9 +84,9 @@ struct MaxJob {
 // Where the potentials of sequence b come from: a dense tensor of TIN, or (MaxStructF) trans[s][t] + emit[b][i][t],
 // the single-precision sum the materialised tensor would hold.  AL: T is a multiple of four (16-byte loads).
 //   first(t): the score of tag t at position 0;
-//   fixed_part(s, t0, f) / piece(i, s, t0, f, o): the four potentials of row s, columns t0 .. t0 + 3 of position i
-//       (columns clamped to the matrix if T is no multiple of four: the caller masks them), f being what fixed_part
-//       returned for that piece;
+//   fixed_part(s, t0, f) / piece(i, s, t0, f, o, followed): the four potentials of row s, columns t0 .. t0 + 3 of
+//       position i (what lies past the end of the row if T is no multiple of four is for the caller to mask), f being
+//       what fixed_part returned for that piece; followed: see Anywhere below, the other sources ignore it;
 //   entries(i, dir, y0, x, v): v[k] = M(y0 + k, x), the entries one lane of the chain wave works on (addresses
 //       clamped into the matrix; what lies outside is masked when it is used, max_entry).
 struct MaxStructF {};
@@ -102,6 +102,7 @@ __device__ __forceinline__ void max_load4(const E* row, int T, int t0, float (&o
 template <typename TIN, bool AL>
 struct MaxSource {
     static constexpr bool kStruct = false;
+    static constexpr bool kQuad = false;
     const TIN* phib;
     size_t TT;
     int T;
@@ -109,7 +110,7 @@ struct MaxSource {
         : phib(static_cast<const TIN*>(a.phi) + (size_t)b * a.N * a.T * a.T), TT((size_t)a.T * a.T), T(a.T) {}
     __device__ __forceinline__ float first(int t) const { return Elem<TIN>::get(phib + t); }
     __device__ __forceinline__ void fixed_part(int, int, float (&f)[4]) const { f[0] = f[1] = f[2] = f[3] = 0.f; }
-    __device__ __forceinline__ void piece(int i, int s, int t0, const float (&)[4], float (&o)[4]) const {
+    __device__ __forceinline__ void piece(int i, int s, int t0, const float (&)[4], float (&o)[4], bool) const {
         max_load4<TIN, AL>(phib + (size_t)i * TT + (size_t)s * T, T, t0, o);
     }
     template <int RPL>
@@ -130,16 +131,44 @@ struct MaxSource {
         }
     }
 };
+// A dense tensor of E whose tag count is no multiple of four (and at least five), every piece of a matrix as one
+// load from wherever it starts: a piece that ends a row brings the first entries of the next row with it (the caller
+// masks them), and the piece that ends a matrix the first of the next matrix.  `followed` (the same for the whole
+// wave) says that there is a next matrix; if there is none, the piece that ends the matrix is loaded from four
+// entries earlier, where the matrix ends, and settle_last() moves its entries to their places when the piece is used.
+template <typename E>
+struct Anywhere {};
+template <typename E, bool AL>
+struct MaxSource<Anywhere<E>, AL> : MaxSource<E, false> {
+    static_assert(!AL, "for tag counts that are no multiple of four");
+    static constexpr bool kQuad = true;
+    using Base = MaxSource<E, false>;
+    __device__ __forceinline__ MaxSource(const VitArgs& a, int b) : Base(a, b) {}
+    __device__ __forceinline__ void piece(int i, int s, int t0, const float (&)[4], float (&o)[4], bool followed) const {
+        const int off = s * Base::T + t0, last = (int)Base::TT - 4;
+        Elem<E>::get4_anywhere(Base::phib + (size_t)i * Base::TT + (followed || off < last ? off : last), o);
+    }
+    // The piece that ends a matrix, loaded from the matrix's last four entries: its T % 4 entries inside the matrix sit
+    // at the end of what was loaded and belong at its front (`mine`: this lane holds that piece).
+    __device__ __forceinline__ void settle_last(bool mine, float& o0, float& o1, float& o2, float o3) const {
+        const int r = 4 - (Base::T & 3);  // 1 .. 3, the same in every lane
+        const float n0 = r == 1 ? o1 : r == 2 ? o2 : o3, n1 = r == 1 ? o2 : o3;
+        o0 = mine ? n0 : o0;
+        o1 = mine ? n1 : o1;
+        o2 = mine ? o3 : o2;
+    }
+};
 template <bool AL>
 struct MaxSource<MaxStructF, AL> {
     static constexpr bool kStruct = true;
+    static constexpr bool kQuad = false;
     const float* emb;
     const float* trans;
     int T;
     __device__ __forceinline__ MaxSource(const VitArgs& a, int b) : emb(a.emit + (size_t)b * a.N * a.T), trans(a.trans), T(a.T) {}
     __device__ __forceinline__ float first(int t) const { return trans[t] + emb[t]; }
     __device__ __forceinline__ void fixed_part(int s, int t0, float (&f)[4]) const { max_load4<float, AL>(trans + (size_t)s * T, T, t0, f); }
-    __device__ __forceinline__ void piece(int i, int, int t0, const float (&f)[4], float (&o)[4]) const {
+    __device__ __forceinline__ void piece(int i, int, int t0, const float (&f)[4], float (&o)[4], bool) const {
         float e[4];
         max_load4<float, AL>(emb + (size_t)i * T, T, t0, e);
 #pragma unroll
@@ -401,9 +430,10 @@ __device__ __forceinline__ void max_helper_wave(const VitArgs& a, const VitSpan&
     const auto load = [&](int j, int p) {
         const int q = w + (j < nj ? j : nj - 1) * W;
         const int i = jb.first + q * jb.sdir;
+        const bool followed = sp.b != a.B - 1 || i != a.N - 1;  // another matrix of the tensor lies behind this one
 #pragma unroll
         for (int m = 0; m < NG; ++m)
-            src.piece(i, grow[m], gcol[m], fixed[MaxSource<TIN, AL>::kStruct ? m : 0], raw[p][m]);
+            src.piece(i, grow[m], gcol[m], fixed[MaxSource<TIN, AL>::kStruct ? m : 0], raw[p][m], followed);
     };
     // Waits until the flag reaches `target` (true) or the chain wave has gone on alone at or before step `q`
     // (false).  The chain wave always does one or the other: each of its own waits is bounded by the poll limit
@@ -434,6 +464,14 @@ __device__ __forceinline__ void max_helper_wave(const VitArgs& a, const VitSpan&
         // the slot is free once the chain wave has finished step q - RING and that step's helper has its pointers
         if (!wait_for(&sh.done, q - S::RING + 1, q) || !wait_for(&sh.kept[slot], q - S::RING + 1, q)) return false;
         double* Ms = &sh.M[slot][0][0][0];
+        if constexpr (MaxSource<TIN, AL>::kQuad) {
+            if (sp.b == a.B - 1 && i == a.N - 1) {  // the last matrix of the tensor: its last piece was loaded from further up
+                const int glast = T * Q - 1;
+#pragma unroll
+                for (int m = 0; m < NG; ++m)
+                    src.settle_last(m == (glast >> 6) && lane == (glast & 63), raw[p][m][0], raw[p][m][1], raw[p][m][2], raw[p][m][3]);
+            }
+        }
 #pragma unroll
         for (int m = 0; m < NG; ++m)
             if ((valid >> m) & 1) {
@@ -547,7 +585,14 @@ static hipError_t launch_max_T(const VitArgs& a, int poll_limit, hipStream_t st)
 }
 template <typename TIN>
 static hipError_t launch_max_src(const VitArgs& a, int poll_limit, hipStream_t st) {
-    return (a.T % 4) == 0 ? launch_max_T<TIN, true>(a, poll_limit, st) : launch_max_T<TIN, false>(a, poll_limit, st);
+    if ((a.T % 4) == 0) return launch_max_T<TIN, true>(a, poll_limit, st);
+    if constexpr (!std::is_same<TIN, MaxStructF>::value) {
+        // (from five tags on: below, a matrix is too small for its last four entries to be a piece's)
+        if (a.T >= 5) return launch_max_T<Anywhere<TIN>, false>(a, poll_limit, st);
+        return launch_max_kernel<16, 16, TIN, false>(a, poll_limit, st);
+    } else {
+        return launch_max_T<TIN, false>(a, poll_limit, st);
+    }
 }
 
 hipError_t launch_lane_max_chains(int dtype, const VitArgs& a, int poll_limit, hipStream_t st) {

@@ -50,17 +50,19 @@ struct BatchSlot {
 template <typename TIN, bool ALIGNED>
 __device__ __forceinline__ void load_batch(const TIN* __restrict__ mat, int T, int row0, int c4, float (&v)[4][4],
                                            bool followed = false) {
+    if (ALIGNED) {
 #pragma unroll
-    for (int k = 0; k < 4; ++k) {
-        const int s = row0 + k;
-        if (ALIGNED) {
+        for (int k = 0; k < 4; ++k) {
+            const int s = row0 + k;
             const TIN* row = mat + (size_t)(s < T ? s : T - 1) * T;
             Elem<TIN>::get4_stream(row + (c4 < T ? c4 : T - 4), v[k]);
-        } else if (followed && T > 1) {
-            load_row4_anywhere<TIN, true>(mat, T, s, c4, v[k]);
-        } else {
-            load_row4_anywhere<TIN, false>(mat, T, s, c4, v[k]);
         }
+    } else if (followed) {  // (more than 128 tags here)
+#pragma unroll
+        for (int k = 0; k < 4; ++k) load_row4_anywhere<TIN, true>(mat, T, row0 + k, c4, v[k]);
+    } else {
+#pragma unroll
+        for (int k = 0; k < 4; ++k) load_row4_anywhere<TIN, false>(mat, T, row0 + k, c4, v[k]);
     }
 }
 template <bool ALIGNED>

@@ -341,16 +341,19 @@ __global__ __launch_bounds__(1024) void viterbi_stream_kernel(VitArgs a) {
         const TIN* mat = phib + (size_t)(first + sdir * (u / NBq)) * TT;
         const bool mat_followed = b != a.B - 1 || first + sdir * (u / NBq) != N - 1;
         const int row0 = kVitBatchRows * (u % NBq) + 4 * wave;
+        if (ALIGNED) {
 #pragma unroll
-        for (int k = 0; k < 4; ++k) {
-            const int s = row0 + k;
-            if (ALIGNED) {
+            for (int k = 0; k < 4; ++k) {
+                const int s = row0 + k;
                 const TIN* row = mat + (size_t)(s < T ? s : T - 1) * T;
                 Elem<TIN>::get4_stream(row + (c4 < T ? c4 : T - 4), ring[slot][k]);
-            } else {  // (entries outside the matrix hold other entries of it: they meet -inf, or are dropped)
-                if (mat_followed && T > 1) load_row4_anywhere<TIN, true>(mat, T, s, c4, ring[slot][k]);
-                else load_row4_anywhere<TIN, false>(mat, T, s, c4, ring[slot][k]);
             }
+        } else if (mat_followed) {  // (entries outside the matrix hold other entries of it: they meet -inf, or are dropped)
+#pragma unroll
+            for (int k = 0; k < 4; ++k) load_row4_anywhere<TIN, true>(mat, T, row0 + k, c4, ring[slot][k]);
+        } else {
+#pragma unroll
+            for (int k = 0; k < 4; ++k) load_row4_anywhere<TIN, false>(mat, T, row0 + k, c4, ring[slot][k]);
         }
     };
     if (dir == 0) {
@@ -545,12 +548,15 @@ __device__ __forceinline__ void viterbi_wave_chain(const VitArgs& a, const VitSp
 #pragma unroll
                 for (int k = 0; k < RPL; ++k) ring[slot][k] = erow[c0 + k < T ? c0 + k : T - 1];
             } else {  // (entries past the end of the row hold other entries of the matrix: they are masked below)
+                const TIN* mat = phib + (size_t)i * TT;
+                if ((sp.b != a.B - 1 || i != a.N - 1) && T > 1) {  // (the same for the whole wave: one scalar branch)
 #pragma unroll
-                for (int k = 0; k < RPL; k += 4) {
-                    float q[4];
-                    if ((sp.b != a.B - 1 || i != a.N - 1) && T > 1) load_row4_anywhere<TIN, true>(phib + (size_t)i * TT, T, sc, c0 + k, q);
-                    else load_row4_anywhere<TIN, false>(phib + (size_t)i * TT, T, sc, c0 + k, q);
-                    ring[slot][k] = q[0]; ring[slot][k + 1] = q[1]; ring[slot][k + 2] = q[2]; ring[slot][k + 3] = q[3];
+                    for (int k = 0; k < RPL; k += 4)
+                        load_row4_anywhere<TIN, true>(mat, T, sc, c0 + k, *reinterpret_cast<float(*)[4]>(&ring[slot][k]));
+                } else {
+#pragma unroll
+                    for (int k = 0; k < RPL; k += 4)
+                        load_row4_anywhere<TIN, false>(mat, T, sc, c0 + k, *reinterpret_cast<float(*)[4]>(&ring[slot][k]));
                 }
             }
         };

@@ -74,17 +74,19 @@ __device__ __forceinline__ void wave_load(const TIN* __restrict__ mat, int T, in
                                           bool followed = false) {
     using W = WGeo<TP>;
     const int c4 = 4 * (lane % W::CG), s0 = W::R * (lane / W::CG);
+    if (ALIGNED) {
 #pragma unroll
-    for (int k = 0; k < W::R; ++k) {
-        const int s = s0 + k;
-        if (ALIGNED) {
+        for (int k = 0; k < W::R; ++k) {
+            const int s = s0 + k;
             const TIN* row = mat + (size_t)(s < T ? s : T - 1) * T;
             Elem<TIN>::get4(row + (c4 < T ? c4 : T - 4), v[k]);
-        } else if (followed && T > 1) {  // (the same for the whole wave: a scalar branch)
-            load_row4_anywhere<TIN, true>(mat, T, s, c4, v[k]);
-        } else {
-            load_row4_anywhere<TIN, false>(mat, T, s, c4, v[k]);
         }
+    } else if (followed && T > 1) {  // (the same for the whole wave: one scalar branch)
+#pragma unroll
+        for (int k = 0; k < W::R; ++k) load_row4_anywhere<TIN, true>(mat, T, s0 + k, c4, v[k]);
+    } else {
+#pragma unroll
+        for (int k = 0; k < W::R; ++k) load_row4_anywhere<TIN, false>(mat, T, s0 + k, c4, v[k]);
     }
 }
 // What has to follow wave_load where the tile is consumed (nothing if the tag count is a multiple of four).

@@ -176,7 +176,7 @@ def test_tag_counts_off_the_16_byte_grid_forbidden_edges_and_jumps(crf, oracle_m
     check_case(crf, oracle_mod, phi, lens, poison=False, algo=crf.ALGO_SEQUENTIAL, what=f"sequential -inf / jumps T={T}")
 
 
-@pytest.mark.parametrize("T", (1, 2, 3, 5, 7, 13, 30, 45, 99, 131, 255))
+@pytest.mark.parametrize("T", (1, 2, 3, 5, 6, 7, 13, 30, 45, 57, 63, 99, 131, 255))
 def test_the_last_matrix_of_the_tensor_with_nothing_usable_behind_it(crf, oracle_mod, T):
     """Full-length sequences, so that the last matrix of the tensor is worked on, in a buffer that holds NaN right
     behind (and before) the tensor: whatever a load of four columns takes in past the end of a row must not reach a
@@ -193,6 +193,17 @@ def test_the_last_matrix_of_the_tensor_with_nothing_usable_behind_it(crf, oracle
                    queries=("logz", "mu") if algo == crf.ALGO_SEQUENTIAL_EXACT else ("logz", "mu", "vit"))
     if 8 <= T <= 48:
         check_case(crf, oracle_mod, phi, None, algo=crf.ALGO_SEQUENTIAL_LANES, what=f"tensor end, lanes T={T}", device_phi=dphi)
+    elif T <= 64:   # (the argmax has chain-wave kernels at every tag count up to 64)
+        check_case(crf, oracle_mod, phi, None, algo=crf.ALGO_SEQUENTIAL_LANES, what=f"tensor end, lanes T={T}", device_phi=dphi,
+                   queries=("vit",))
+    if T <= 64:     # bfloat16 too: rows at any multiple of two bytes
+        phih, _ = workloads.random_case(2850 + T, B, N, T, scale=3.0, dtype="bf16")
+        bufh = torch.full((n + 64,), float("nan"), device="cuda:0", dtype=torch.bfloat16)
+        bufh[32:32 + n] = phih.reshape(-1).to("cuda:0")
+        dphih = bufh[32:32 + n].view(B, N, T, T)
+        check_case(crf, oracle_mod, phih, None, algo=crf.ALGO_SEQUENTIAL, what=f"tensor end bf16 T={T}", device_phi=dphih)
+        check_case(crf, oracle_mod, phih, None, algo=crf.ALGO_SEQUENTIAL_LANES, what=f"tensor end bf16, lanes T={T}", device_phi=dphih,
+                   queries=("logz", "mu", "vit") if 8 <= T <= 48 else ("vit",))
 
 
 @pytest.mark.parametrize("T", [255, 256, 129, 200])
