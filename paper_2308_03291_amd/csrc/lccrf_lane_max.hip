@@ -70,6 +70,7 @@ struct MaxShared {
                                            // 65: the helpers' scattered writes of one instruction spread over the banks)
     double V[kMaxVecRing][TP];             // V_q, the vector that enters step q, at [q % kMaxVecRing]
     double own[2][TP];                     // the vectors of a chain wave that goes on alone
+    float emis[kMaxHelpers][64];           // structured potentials: the emission scores of the position a helper works on
     int ready[S::RING];                    // q + 1 once the matrix of step q sits in slot q % RING
     int kept[S::RING];                     // q + 1 once the helper of step q has read the matrix back for its pointers
     int done;                              // steps the chain wave has finished (V_done is published)
@@ -174,6 +175,7 @@ struct MaxSource<MaxStructF, AL> {
 #pragma unroll
         for (int k = 0; k < 4; ++k) o[k] = f[k] + e[k];
     }
+    __device__ __forceinline__ float emission(int i, int t) const { return emb[(size_t)i * T + (t < T ? t : T - 1)]; }
     template <int RPL>
     __device__ __forceinline__ void entries(int i, int dir, int y0, int x, float (&v)[RPL]) const {
         const int xc = x < T ? x : T - 1;
@@ -421,19 +423,27 @@ __device__ __forceinline__ void max_helper_wave(const VitArgs& a, const VitSpan&
         grow[m] = s_;
         gcol[m] = t0;
     }
-    float raw[2][NG][4];
-    float fixed[MaxSource<TIN, AL>::kStruct ? NG : 1][4];  // structured potentials: this lane's entries of the transition matrix
-    if constexpr (MaxSource<TIN, AL>::kStruct) {
+    // Dense potentials: the lane's pieces of two matrices, one in hand, one in flight.  Structured potentials: the
+    // lane's entries of the transition matrix once, and of a position only the emission score of tag `lane` (one
+    // load a matrix): the helper spreads the scores of a position over its lanes through LDS when it works on it.
+    constexpr bool kStruct = MaxSource<TIN, AL>::kStruct;
+    float raw[kStruct ? 1 : 2][kStruct ? 1 : NG][4];
+    float fixed[kStruct ? NG : 1][4];
+    float emis[2] = {0.f, 0.f};
+    if constexpr (kStruct) {
 #pragma unroll
         for (int m = 0; m < NG; ++m) src.fixed_part(grow[m], gcol[m], fixed[m]);
     }
     const auto load = [&](int j, int p) {
         const int q = w + (j < nj ? j : nj - 1) * W;
         const int i = jb.first + q * jb.sdir;
-        const bool followed = sp.b != a.B - 1 || i != a.N - 1;  // another matrix of the tensor lies behind this one
+        if constexpr (kStruct) {
+            emis[p] = src.emission(i, lane);
+        } else {
+            const bool followed = sp.b != a.B - 1 || i != a.N - 1;  // another matrix of the tensor lies behind this one
 #pragma unroll
-        for (int m = 0; m < NG; ++m)
-            src.piece(i, grow[m], gcol[m], fixed[MaxSource<TIN, AL>::kStruct ? m : 0], raw[p][m], followed);
+            for (int m = 0; m < NG; ++m) src.piece(i, grow[m], gcol[m], fixed[0], raw[p][m], followed);
+        }
     };
     // Waits until the flag reaches `target` (true) or the chain wave has gone on alone at or before step `q`
     // (false).  The chain wave always does one or the other: each of its own waits is bounded by the poll limit
@@ -472,12 +482,21 @@ __device__ __forceinline__ void max_helper_wave(const VitArgs& a, const VitSpan&
                     src.settle_last(m == (glast >> 6) && lane == (glast & 63), raw[p][m][0], raw[p][m][1], raw[p][m][2], raw[p][m][3]);
             }
         }
+        if constexpr (kStruct) sh.emis[w][lane] = emis[p];  // (read back below by this wave only: its LDS instructions run in order)
 #pragma unroll
         for (int m = 0; m < NG; ++m)
             if ((valid >> m) & 1) {
                 double d[4];
+                if constexpr (kStruct) {
+                    const float4 e = *reinterpret_cast<const float4*>(&sh.emis[w][gcol[m]]);
+                    d[0] = max_entry(fixed[m][0] + e.x, true);
+                    d[1] = max_entry(fixed[m][1] + e.y, AL || gcol[m] + 1 < T);
+                    d[2] = max_entry(fixed[m][2] + e.z, AL || gcol[m] + 2 < T);
+                    d[3] = max_entry(fixed[m][3] + e.w, AL || gcol[m] + 3 < T);
+                } else {
 #pragma unroll
-                for (int k = 0; k < 4; ++k) d[k] = max_entry(raw[p][m][k], AL || gcol[m] + k < T);  // (-inf past the last column)
+                    for (int k = 0; k < 4; ++k) d[k] = max_entry(raw[p][m][k], AL || gcol[m] + k < T);  // (-inf past the last column)
+                }
                 if (jb.dir == 0) {  // four columns of one source tag: 16 bytes apart
 #pragma unroll
                     for (int k = 0; k < 4; ++k) Ms[lidx[m] + 2 * k] = d[k];
@@ -516,8 +535,11 @@ __device__ __forceinline__ void max_helper_wave(const VitArgs& a, const VitSpan&
     flush();
 }
 
+// (At 17 .. 32 tags two workgroups share a compute unit, four waves a SIMD: 128 vector registers a lane.  The aligned
+// dense kernels need fewer anyway; the others spill a few values of their chain wave's lone path for it and gain a
+// fifth on batches of more than one sequence for every two compute units: B=256 N=128 T=30 56 -> 48 us.)
 template <int TP, int ROWS, typename TIN, bool AL>
-__global__ __launch_bounds__(64 * kMaxWaves) void viterbi_lane_kernel(VitArgs a, int poll_limit) {
+__global__ __launch_bounds__(64 * kMaxWaves, (TP == 32 ? 4 : 1)) void viterbi_lane_kernel(VitArgs a, int poll_limit) {
     using S = MaxShape<TP, ROWS>;
     extern __shared__ __attribute__((aligned(16))) unsigned char max_smem[];
     MaxShared<TP, ROWS>& sh = *reinterpret_cast<MaxShared<TP, ROWS>*>(max_smem);
