@@ -688,13 +688,14 @@ __global__ __launch_bounds__(G::W) void chain_half_kernel(ChainArgs a) {
     }
     auto load = [&](int i, int slot) {
         if constexpr (CAN_STRUCT) {
-            load_emit4<ALIGNED>(emb + (size_t)i * T, T, c4, ring[slot][0]);
+            load_emit4<ALIGNED>(emb + (size_t)i * T, T, c4, ring[slot][0], b != a.B - 1 || i != N - 1);
             return;
         }
         load_tile<G, TIN, ALIGNED>(phib + (size_t)i * TT, T, c4, r0, ring[slot], b != a.B - 1 || i != N - 1);
     };
     auto tile_ready = [&](int slot) {  // turns a slot that holds emissions into the tile
         if constexpr (CAN_STRUCT) {
+            settle_emit4<ALIGNED>(ring[slot][0], T, c4);
             add_trans<ITEMS>(ring[slot], tr);
         } else {
             settle_tile<G, ALIGNED>(ring[slot], T, c4);
@@ -815,13 +816,14 @@ __global__ __launch_bounds__(G::W) void chain_marginal_kernel(ChainArgs a) {
     }
     auto load_phi = [&](int i, int slot) {
         if constexpr (CAN_STRUCT) {
-            load_emit4<ALIGNED>(emb + (size_t)i * T, T, c4, ring[slot][0]);
+            load_emit4<ALIGNED>(emb + (size_t)i * T, T, c4, ring[slot][0], b != a.B - 1 || i != N - 1);
             return;
         }
         load_tile<G, TIN, ALIGNED>(phib + (size_t)i * TT, T, c4, r0, ring[slot], b != a.B - 1 || i != N - 1);
     };
     auto tile_ready = [&](int slot) {
         if constexpr (CAN_STRUCT) {
+            settle_emit4<ALIGNED>(ring[slot][0], T, c4);
             add_trans<ITEMS>(ring[slot], tr);
         } else {
             settle_tile<G, ALIGNED>(ring[slot], T, c4);

@@ -173,15 +173,24 @@ __device__ __forceinline__ void settle_tile(float (&v)[G::ITEMS][4], int T, int 
 // transition tile stays in registers (loaded once with load_tile / wave_load), a position brings
 // only its T emission scores.  load_emit4 puts this thread's four columns into row 0 of the slot;
 // add_trans then turns the slot into the tile of that position.
+// (T no multiple of four: the columns a settled tile of the transition matrix holds, see load_row4_anywhere; as one
+// load if another row of emission scores follows this one in memory (`followed`, the same for the whole workgroup),
+// what it brings in from that row being replaced by settle_row4() before add_trans; element by element otherwise.)
 template <bool ALIGNED>
-__device__ __forceinline__ void load_emit4(const float* __restrict__ emit_row, int T, int c4, float (&o)[4]) {
+__device__ __forceinline__ void load_emit4(const float* __restrict__ emit_row, int T, int c4, float (&o)[4], bool followed = false) {
     if (ALIGNED) {
         Elem<float>::get4(emit_row + (c4 < T ? c4 : T - 4), o);
-    } else {  // (the columns a settled tile of the transition matrix holds: see load_row4_anywhere)
+    } else if (followed && T >= 4) {
+        Elem<float>::get4_anywhere(emit_row + (c4 < T ? c4 : 0), o);
+    } else {
         const int cc = c4 < T ? c4 : 0;
 #pragma unroll
         for (int j = 0; j < 4; ++j) o[j] = emit_row[cc + j < T ? cc + j : cc];
     }
+}
+template <bool ALIGNED>
+__device__ __forceinline__ void settle_emit4(float (&o)[4], int T, int c4) {
+    if constexpr (!ALIGNED) settle_row4(o, T, c4);
 }
 template <int ROWS>
 __device__ __forceinline__ void add_trans(float (&v)[ROWS][4], const float (&tr)[ROWS][4]) {

@@ -87,13 +87,14 @@ __global__ __launch_bounds__(G::W) void viterbi_half_kernel(VitArgs a) {
     // forward: column maxima over rows, merged across waves through LDS
     auto fetch = [&](int i, float (&v)[ITEMS][4]) {
         if constexpr (CAN_STRUCT) {
-            load_emit4<ALIGNED>(emb + (size_t)i * T, T, c4, v[0]);
+            load_emit4<ALIGNED>(emb + (size_t)i * T, T, c4, v[0], b != a.B - 1 || i != N - 1);
             return;
         }
         load_tile<G, TIN, ALIGNED>(phib + (size_t)i * TT, T, c4, r0, v, b != a.B - 1 || i != N - 1);
     };
     auto tile_ready = [&](float (&v)[ITEMS][4]) {
         if constexpr (CAN_STRUCT) {
+            settle_emit4<ALIGNED>(v[0], T, c4);
             add_trans<ITEMS>(v, tr);
         }
     };

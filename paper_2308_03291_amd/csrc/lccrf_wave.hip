@@ -101,8 +101,14 @@ __device__ __forceinline__ void wave_settle(float (&v)[WGeo<TP>::R][4], int T, i
 
 // The same lane's share of an emission row (row 0 of the slot) for structured potentials.
 template <int TP, bool ALIGNED>
-__device__ __forceinline__ void wave_load_emit(const float* __restrict__ emit_row, int T, int lane, float (&v)[WGeo<TP>::R][4]) {
-    load_emit4<ALIGNED>(emit_row, T, 4 * (lane % WGeo<TP>::CG), v[0]);
+__device__ __forceinline__ void wave_load_emit(const float* __restrict__ emit_row, int T, int lane, float (&v)[WGeo<TP>::R][4],
+                                               bool followed = false) {
+    load_emit4<ALIGNED>(emit_row, T, 4 * (lane % WGeo<TP>::CG), v[0], followed);
+}
+// What has to come between wave_load_emit and add_trans (nothing if the tag count is a multiple of four).
+template <int TP, bool ALIGNED>
+__device__ __forceinline__ void wave_settle_emit(float (&v)[WGeo<TP>::R][4], int T, int lane) {
+    settle_emit4<ALIGNED>(v[0], T, 4 * (lane % WGeo<TP>::CG));
 }
 
 __device__ __forceinline__ float max4(const float (&x)[4]) { return fmaxf(fmaxf(x[0], x[1]), fmaxf(x[2], x[3])); }
@@ -365,7 +371,7 @@ __device__ __forceinline__ void wave_half_body(const ChainArgs& a, const Span& s
         wave_settle<TP, ALIGNED>(tr, T, lane);
     }
     auto load = [&](int i, int slot) {
-        if constexpr (structured) wave_load_emit<TP, ALIGNED>(emb + (size_t)i * T, T, lane, ring[slot]);
+        if constexpr (structured) wave_load_emit<TP, ALIGNED>(emb + (size_t)i * T, T, lane, ring[slot], b != a.B - 1 || i != N - 1);
         else wave_load<TP, TIN, ALIGNED>(phib + (size_t)i * TT, T, lane, ring[slot], b != a.B - 1 || i != N - 1);
     };
     const float none4[4] = {0.f, 0.f, 0.f, 0.f};
@@ -402,7 +408,10 @@ __device__ __forceinline__ void wave_half_body(const ChainArgs& a, const Span& s
         };
         float hc[4] = {0.f, 0.f, 0.f, 0.f};  // entropy of the path behind each tag, column form
         walk<PF>(p0 + 1, h, +1, load, [&](int i, int slot) {
-            if constexpr (structured) add_trans<R>(ring[slot], tr);
+            if constexpr (structured) {
+                wave_settle_emit<TP, ALIGNED>(ring[slot], T, lane);
+                add_trans<R>(ring[slot], tr);
+            }
             else wave_settle<TP, ALIGNED>(ring[slot], T, lane);
             const float d = settle(i - 1);
             float ua[R], hrow[R];
@@ -446,7 +455,10 @@ __device__ __forceinline__ void wave_half_body(const ChainArgs& a, const Span& s
 #pragma unroll
         for (int k = 0; k < R; ++k) hr[k] = 0.f;
         walk<PF>(e, h + 1, -1, load, [&](int i, int slot) {
-            if constexpr (structured) add_trans<R>(ring[slot], tr);
+            if constexpr (structured) {
+                wave_settle_emit<TP, ALIGNED>(ring[slot], T, lane);
+                add_trans<R>(ring[slot], tr);
+            }
             else wave_settle<TP, ALIGNED>(ring[slot], T, lane);
             const float d = settle(i);
             float ub[4], hcol[4];
@@ -539,7 +551,7 @@ __device__ __forceinline__ void wave_marginal_body(const ChainArgs& a, const Spa
     const bool difference = a.ent_kind == 3;
     float ringq[ENT == 2 ? PF : 1][R][4];
     auto load_phi = [&](int i, int slot) {
-        if constexpr (structured) wave_load_emit<TP, ALIGNED>(emb + (size_t)i * T, T, lane, ring[slot]);
+        if constexpr (structured) wave_load_emit<TP, ALIGNED>(emb + (size_t)i * T, T, lane, ring[slot], b != a.B - 1 || i != N - 1);
         else wave_load<TP, TIN, ALIGNED>(phib + (size_t)i * TT, T, lane, ring[slot], b != a.B - 1 || i != N - 1);
         if constexpr (ENT == 2) wave_load<TP, TIN, ALIGNED>(psib + (size_t)i * TT, T, lane, ringq[slot], b != a.B - 1 || i != N - 1);
     };
@@ -572,7 +584,10 @@ __device__ __forceinline__ void wave_marginal_body(const ChainArgs& a, const Spa
             ob[slot] = vs.Ob[i - og];
         };
         walk<PF>(h + 1, e, +1, load, [&](int i, int slot) {
-            if constexpr (structured) add_trans<R>(ring[slot], tr);
+            if constexpr (structured) {
+                wave_settle_emit<TP, ALIGNED>(ring[slot], T, lane);
+                add_trans<R>(ring[slot], tr);
+            }
             else wave_settle<TP, ALIGNED>(ring[slot], T, lane);
             if constexpr (ENT == 2) wave_settle<TP, ALIGNED>(ringq[slot], T, lane);
             const float d = finite_or_zero(xor_max<1, W::CG>(max4(vc)));
@@ -603,7 +618,10 @@ __device__ __forceinline__ void wave_marginal_body(const ChainArgs& a, const Spa
             oa[slot] = vs.Oa[i - 1 - og];
         };
         walk<PF>(h, p0 + 1, -1, load, [&](int i, int slot) {
-            if constexpr (structured) add_trans<R>(ring[slot], tr);
+            if constexpr (structured) {
+                wave_settle_emit<TP, ALIGNED>(ring[slot], T, lane);
+                add_trans<R>(ring[slot], tr);
+            }
             else wave_settle<TP, ALIGNED>(ring[slot], T, lane);
             if constexpr (ENT == 2) wave_settle<TP, ALIGNED>(ringq[slot], T, lane);
             float m = vr[0];

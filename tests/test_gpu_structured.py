@@ -62,6 +62,18 @@ def test_structured_sweep(crf, oracle_mod, T, N):
     _check(crf, oracle_mod, emit, trans, lens, f"structured T={T} N={N}")
 
 
+@pytest.mark.parametrize("T", (9, 13, 21, 30, 45, 63))
+def test_structured_big_batches_off_the_16_byte_grid(crf, oracle_mod, T):
+    """More sequences than the chain-wave kernels take: the one-wave and four-wave kernels with a tag count that is
+    no multiple of four (a row of emission scores loaded as one piece a lane where another row follows it, element
+    by element for the last row of the tensor: full lengths, so that row is worked on)."""
+    B, N = 300, 12
+    for op in (crf.OP_MARGINALS, crf.OP_ARGMAX):
+        assert crf.auto_algo(op, B, N, T) == crf.ALGO_SEQUENTIAL
+    emit, trans = _make(7100 + T, B, N, T)
+    _check(crf, oracle_mod, emit, trans, None, f"structured B={B} T={T}")
+
+
 def test_structured_config3(crf, oracle_mod):
     """Config 3 is exactly this structure (emissions of scale 2 plus one transition matrix)."""
     w = workloads.WORKLOADS["cfg3"]
