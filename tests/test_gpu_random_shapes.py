@@ -48,3 +48,36 @@ def test_random_shape(crf, oracle_mod, k, B, N, T, scale, dtype, ragged, chunk):
             check_two_chains(crf, oracle_mod, phi, q, lens if ragged else None, what)
     finally:
         crf.set_scan_chunk(0)
+
+
+def _off_grid_cases(seed, count):
+    rng = np.random.default_rng(seed)
+    tags = [6, 9, 10, 11, 13, 14, 18, 21, 22, 23, 27, 30, 35, 37, 41, 45, 46, 50, 55, 61, 70, 99, 131, 190, 201, 255]
+    out = []
+    for k in range(count):
+        T = int(tags[k % len(tags)])
+        N = int(rng.integers(1, max(2, min(120, 5000 // T))))
+        B = int(rng.integers(1, 6))
+        scale = float(rng.choice([0.3, 1.0, 3.0, 8.0]))
+        dtype = "bf16" if rng.random() < 0.35 else "f32"
+        ragged = rng.random() < 0.5          # (unragged: the last matrix of the tensor is worked on)
+        out.append((k, B, N, T, scale, dtype, ragged))
+    return out
+
+
+@pytest.mark.parametrize("k,B,N,T,scale,dtype,ragged", _off_grid_cases(20230804, 78))
+def test_random_shape_off_the_16_byte_grid(crf, oracle_mod, k, B, N, T, scale, dtype, ragged):
+    """Tag counts that are no multiple of four, every schedule that serves the shape: the rows of a matrix start at
+    any multiple of the element size, and the kernels load pieces of four columns from wherever they start."""
+    phi, lens = workloads.random_case(90000 + k, B, N, T, scale=scale, ragged=ragged, min_len=0, dtype=dtype)
+    what = f"off-grid case {k}: B={B} N={N} T={T} scale={scale} {dtype}"
+    algos = [crf.ALGO_AUTO, crf.ALGO_SEQUENTIAL]
+    if T <= 64:
+        algos.append(crf.ALGO_SCAN)
+    for algo in algos:
+        q = ("logz", "mu", "vit") if algo != crf.ALGO_SCAN or T <= 16 else ("logz", "mu")
+        check_case(crf, oracle_mod, phi, lens if ragged else None, poison=(dtype == "f32"), algo=algo, what=f"{what} algo={algo}", queries=q)
+    if T <= 64:
+        q = ("logz", "mu", "vit") if 8 <= T <= 48 else ("vit",)
+        check_case(crf, oracle_mod, phi, lens if ragged else None, poison=(dtype == "f32"), algo=crf.ALGO_SEQUENTIAL_LANES,
+                   what=f"{what} lanes", queries=q)
