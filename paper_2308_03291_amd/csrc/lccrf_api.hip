@@ -196,27 +196,51 @@ int check_common(const void* phi, int dt, int B, int N, int T, const void* ws, s
 // the whole batch, which cross near 450 sequences; with 17 .. 32 tags a chunk product costs eight
 // times the matrix instructions and the scan wins up to about 32768 positions a batch (the paper's
 // own benchmark size, 128 x 256, is the limit).
+//
+// Long chains pay whatever the batch holds, as long as the batch is small: the sequential schedule's time grows
+// with the length of the longest chain, the scan's with the positions of the whole batch.  Measured, log-partition
+// (us; one-wave or four-wave kernels / scan): 17 .. 32 tags 0.26 N / 30 + 0.0016 B N (B=4 N=16384 T=32 4257 / 164,
+// B=64 N=2048 549 / 236, B=128 N=1024 280 / 225); 33 .. 48 tags 0.36 N / 30 + 0.0075 B N (B=8 N=4096 T=48
+// 1491 / 293, B=32 N=1024 387 / 277); 49 .. 64 tags 0.37 N / 45 + 0.013 B N (B=16 N=1024 T=64 385 / 258).
 inline bool scan_pays_sum(int B, int N, int T) {
     if (!lccrf::scan_supported(T) || N < 8 * scan_chunk(B, N, T)) return false;
+    if (T <= 16) return B <= 448;
+    const double n = (double)N, pb = (double)B;
     // 33 .. 64 tags: a position of a chunk product costs a compute unit about 2.4 us (36 to 64 matrix
     // instructions a wave beside as many exponentials), which the shorter chains pay back up to about 8192
     // positions a batch (B=32, N=256, T=48: marginals 285 -> 124 us; B=128, N=128, T=48: 148 -> 206 us).
-    if (T > 32) return (long long)B * N <= 8192;
-    return T <= 16 ? B <= 448 : (long long)B * N <= 32768;
+    if (T > 48) return (long long)B * N <= 8192 || n * (0.37 - 0.013 * pb) > 45.0;
+    if (T > 32) return (long long)B * N <= 8192 || n * (0.36 - 0.0075 * pb) > 30.0;
+    return (long long)B * N <= 32768 || n * (0.26 - 0.0016 * pb) > 30.0;
 }
 // The max-plus scan (16 tags at most) pays its chunk products in double-precision vector
 // instructions: it takes chains twice as long to pay, and at most 65536 positions a batch
 // (B=256, N=256: 86 us against 62 sequential; B=128, N=512: 87 against 114).
+// Longer chains pay in larger batches too: the one-wave kernels take about 0.2 us a position of the longest chain,
+// the scan 40 us + 0.75 ns a position of the batch (B=32 N=4096 805 / 140, B=16 N=16384 3193 / 239).
 inline bool scan_pays_max(int B, int N, int T) {
-    return lccrf::scan_supported_max(T) && N >= 16 * scan_chunk(B, N, T) && (long long)B * N <= 65536;
+    if (!lccrf::scan_supported_max(T) || N < 16 * scan_chunk(B, N, T)) return false;
+    return (long long)B * N <= 65536 || (double)N * (0.195 - 0.00075 * B) > 40.0;
 }
 // The entropy-like queries make two passes under the scan against one sequential pass: with 17 .. 32
 // tags it takes chains twice as long to pay.
+// (Long chains at 17 .. 32 tags: one sequential pass 0.43 us a position of the longest chain, the scan's two about
+// 20 us + 3 ns a position of the batch: B=64 N=1024 T=24 437 us sequential, B=64 N=2048 T=32 396 under the scan.)
 inline bool scan_pays_entropy(int B, int N, int T) {
-    return T <= 32 && scan_pays_sum(B, N, T) && (T <= 16 || N >= 16 * scan_chunk(B, N, T));
+    if (T > 32 || !lccrf::scan_supported(T)) return false;
+    if (T <= 16) return scan_pays_sum(B, N, T);
+    if (N < 16 * scan_chunk(B, N, T)) return false;
+    return (long long)B * N <= 32768 || (double)N * (0.42 - 0.003 * B) > 30.0;
 }
 // Sampling under the scan runs every chunk's forward chain with the one-wave kernels (32 tags at most).
-inline bool scan_pays_sample(int B, int N, int T) { return T <= 32 && scan_pays_sum(B, N, T); }
+// (Long chains at 17 .. 32 tags: 0.7 us a position of the longest chain sequentially, 30 us + 4 ns a position of
+// the batch under the scan: B=128 N=1024 T=32 767 us sequential, B=64 N=2048 510 under the scan.)
+inline bool scan_pays_sample(int B, int N, int T) {
+    if (T > 32 || !lccrf::scan_supported(T)) return false;
+    if (T <= 16) return scan_pays_sum(B, N, T);
+    if (N < 8 * scan_chunk(B, N, T)) return false;
+    return (long long)B * N <= 32768 || (double)N * (0.7 - 0.004 * B) > 30.0;
+}
 
 // Whether LCCRF_ALGO_AUTO takes the chain-wave / producer-wave kernels (lccrf_lane.hip) for a sum query
 // (op 0: log-partition, 1: marginals).  Their time is set by the serial depth alone, about 12 us plus 0.35 us
@@ -238,12 +262,22 @@ inline bool lanes_pay_sum(int op, int B, int N, int T) {
         if (B > cus || N < 16) return false;
         return !scan_pays_sum(B, N, T) || (double)N * (0.24 - 0.00075 * B) < 10.0;
     }
+    // Against the scan, where it would be taken (us, log-partition / marginals; these kernels and the scan):
+    // 17 .. 32 tags 15 + 0.124 N / 20 + 0.257 N and 30 + 0.0016 B N / 40 + 0.0035 B N (B=16 N=4096 T=32 521 / 1054
+    // and 139 / 271, B=64 N=1024 144 / 282 and 128 / 259, B=128 N=1024 146 / 343 and 225 / 483);
+    // 33 .. 48 tags 15 + 0.18 N / 20 + 0.41 N and 30 + 0.0075 B N / 100 + 0.0107 B N (B=16 N=2048 T=48 379 / 858
+    // and 283 / 471, B=32 N=1024 200 / 449 and 277 / 453); 49 .. 64 tags, log-partition, 15 + 0.2 N and
+    // 45 + 0.013 B N (B=16 N=1024 T=64 218 and 258).
+    const double n = (double)N;
     if (T <= 32) {
         if (B > cus) return false;
-        return !scan_pays_sum(B, N, T) || (double)N * (0.35 - 0.0029 * B) < 18.0;
+        if (!scan_pays_sum(B, N, T)) return true;
+        return op == 0 ? n * (0.124 - 0.0016 * B) < 15.0 : n * (0.257 - 0.0035 * B) < 20.0;
     }
-    if (2 * B > cus || scan_pays_sum(B, N, T)) return false;
-    return T <= 48 || op == 0;
+    if (2 * B > cus || (T > 48 && op != 0)) return false;
+    if (!scan_pays_sum(B, N, T)) return true;
+    if (T > 48) return n * (0.2 - 0.013 * B) < 30.0;
+    return op == 0 ? n * (0.18 - 0.0075 * B) < 15.0 : n * (0.41 - 0.0107 * B) < 80.0;
 }
 
 // Whether LCCRF_ALGO_AUTO gives the max-plus chains to the chain-wave kernels (lccrf_lane_max.hip) rather than to
@@ -262,11 +296,11 @@ inline bool lanes_pay_max(int B, int N, int T) {
 }
 // Whether AUTO takes the max-plus scan: where it would pay against the one-wave kernels, unless the chain-wave
 // kernels are quicker still (up to 16 tags they take about 16 us + 0.084 us a position whatever the batch, the
-// scan about 40 us + 6 ns a position of a sequence + 0.5 ns a position of the batch: B=64 N=512 59 / 61,
-// B=64 N=768 80 / 74, B=8 N=512 58 / 45, B=128 N=512 61 / 76, B=256 N=256 41 / 75).
+// scan about 40 us + 0.75 ns a position of the batch: B=64 N=512 59 / 61, B=64 N=768 80 / 74, B=8 N=512 58 / 45,
+// B=128 N=512 61 / 76, B=256 N=256 41 / 75, B=128 N=2048 190 / 254, B=64 N=4096 358 / 237, B=16 N=16384 1368 / 239).
 inline bool scan_taken_max(int B, int N, int T) {
     if (!scan_pays_max(B, N, T)) return false;
-    return !(lanes_pay_max(B, N, T) && (double)N * (0.078 - 0.0005 * B) < 24.0);
+    return !(lanes_pay_max(B, N, T) && (double)N * (0.084 - 0.00075 * B) < 24.0);
 }
 
 int sum_query(int op, const void* phi, int dt, const int32_t* lengths, int B, int N, int T, float* logZ,

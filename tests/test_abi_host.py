@@ -77,6 +77,13 @@ def test_auto_schedule_is_reported_without_a_gpu(lib):
     assert binding.auto_algo(binding.OP_MARGINALS, 32, 256, 48) == binding.ALGO_SCAN         # 33 .. 64 tags, small batch
     assert binding.auto_algo(binding.OP_ENTROPY, 32, 256, 48) == binding.ALGO_SEQUENTIAL     # entropy by edges: 32 tags at most
     assert binding.auto_algo(binding.OP_SAMPLE, 32, 256, 48) == binding.ALGO_SEQUENTIAL
+    # long chains pay whatever the batch holds, while the batch is small
+    assert binding.auto_algo(binding.OP_MARGINALS, 4, 16384, 32) == binding.ALGO_SCAN
+    assert binding.auto_algo(binding.OP_LOGZ, 128, 1024, 32) == binding.ALGO_SCAN
+    assert binding.auto_algo(binding.OP_LOGZ, 256, 4096, 32) == binding.ALGO_SEQUENTIAL
+    assert binding.auto_algo(binding.OP_MARGINALS, 8, 4096, 48) == binding.ALGO_SCAN
+    assert binding.auto_algo(binding.OP_MARGINALS, 64, 4096, 48) == binding.ALGO_SEQUENTIAL
+    assert binding.auto_algo(binding.OP_MARGINALS, 16, 1024, 64) == binding.ALGO_SCAN
     with pytest.raises(binding.LccrfError):
         binding.auto_algo(binding.OP_MARGINALS, 1, 8, 0)
     with pytest.raises(binding.LccrfError):

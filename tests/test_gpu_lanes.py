@@ -147,3 +147,23 @@ def test_lanes_agree_with_the_one_wave_schedule(crf):
     assert float((mu_a - mu_b).abs().max()) < 4e-6
     s = mu_a.sum(dim=(2, 3))
     assert float((s - 1).abs().max()) < 2e-5
+
+
+def test_auto_between_the_chain_wave_kernels_and_the_scan_on_long_chains(crf):
+    """lccrf_auto_algo on a 256-unit device: the chain-wave kernels' time grows with the length of the chains, the
+    scan's with the positions of the whole batch; long chains in small batches go to the scan, larger batches of the
+    same length stay."""
+    A = crf.auto_algo
+    for op in (crf.OP_LOGZ, crf.OP_MARGINALS):
+        assert A(op, 4, 16384, 32) == crf.ALGO_SCAN
+        assert A(op, 16, 4096, 32) == crf.ALGO_SCAN
+        assert A(op, 64, 2048, 32) == crf.ALGO_SCAN
+        assert A(op, 128, 1024, 32) == crf.ALGO_SEQUENTIAL_LANES
+        assert A(op, 128, 256, 32) == crf.ALGO_SEQUENTIAL_LANES      # the paper's shape
+        assert A(op, 8, 4096, 48) == crf.ALGO_SCAN
+        assert A(op, 16, 2048, 48) == crf.ALGO_SCAN
+        assert A(op, 32, 1024, 48) == crf.ALGO_SEQUENTIAL_LANES
+        assert A(op, 128, 128, 48) == crf.ALGO_SEQUENTIAL_LANES      # config 3
+    assert A(crf.OP_LOGZ, 16, 1024, 64) == crf.ALGO_SEQUENTIAL_LANES
+    assert A(crf.OP_MARGINALS, 16, 1024, 64) == crf.ALGO_SCAN
+    assert A(crf.OP_MARGINALS, 32, 1024, 64) == crf.ALGO_SEQUENTIAL

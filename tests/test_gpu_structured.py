@@ -194,8 +194,8 @@ def _scan_lens(N, k):
 
 
 @pytest.mark.parametrize("k", [0, 4, 7])
-@pytest.mark.parametrize("T,N", [(1, 70), (5, 130), (13, 257), (16, 300), (17, 90), (32, 140), (33, 64), (45, 100),
-                                 (48, 96), (64, 130), (63, 71)])
+@pytest.mark.parametrize("T,N", [(1, 70), (5, 130), (13, 257), (16, 300), (17, 120), (32, 140), (33, 300), (45, 320),
+                                 (48, 288), (64, 130), (63, 71)])
 def test_structured_under_the_scan(crf, oracle_mod, chunk, T, N, k):
     """Long chains in small batches: the structured calls take the chunked scan (sum queries up to 64 tags, the argmax
     up to 16; the dense argmax may prefer its chain-wave kernels there, which structured potentials do not have)
@@ -219,7 +219,7 @@ def test_structured_scan_many_chunks(crf, oracle_mod, chunk, T, N, k):
     _check(crf, oracle_mod, emit, trans, lens, f"structured scan, many chunks, T={T} N={N} k={k}")
 
 
-@pytest.mark.parametrize("T,N", [(9, 200), (16, 160), (24, 100), (40, 80)])
+@pytest.mark.parametrize("T,N", [(9, 200), (16, 160), (24, 120), (40, 256)])
 def test_structured_scan_with_forbidden_transitions_and_peaked_emissions(crf, oracle_mod, T, N):
     """-inf transitions (the zero pattern of the chunk products) and emissions of scale 12 (the single-precision
     product gives up, the double-precision one or the exact one takes over)."""
