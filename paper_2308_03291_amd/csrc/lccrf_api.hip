@@ -87,6 +87,19 @@ inline int scan_chunk(long long B, long long N, long long T) {
     return 32;
 }
 
+// The chunk of the max-plus scan: the sum scan's up to 16 tags; at 17 .. 32 tags its chunk products hold two waves a
+// SIMD (one workgroup each), which hide what a lone wave waits for: up to 2048 chunks (B=8 N=4096 T=32: chunk
+// products 210 us with 1024 chunks of 32, 130 us with 2048 of 16; a third wave a SIMD, which needs single LDS tiles
+// and a shallower ring of loads, cost more than it hid: 160 us).
+inline int scan_chunk_max(long long B, long long N, long long T) {
+    if (T <= 16) return scan_chunk(B, N, T);
+    if (const int user = t_snapshot_depth > 0 ? t_scan_chunk_user : g_scan_chunk_user.load(std::memory_order_relaxed))
+        return user;
+    for (int c = 8; c < 32; c *= 2)
+        if (B * ((N + c - 1) / c) <= 2048) return c;
+    return 32;
+}
+
 struct SumWorkspace {
     size_t ua, ub, Oa, Ob, mail, failed;
     size_t Pl, rel, base, Fv, OF, Gv, OG;  // chunked scan (T <= 32 only, else empty)
@@ -138,25 +151,26 @@ inline SumWorkspace sum_workspace(size_t B, size_t N, size_t T) {
 }
 struct MaxWorkspace {
     size_t bp, mid;
-    size_t Mx, K, pin;  // chunked scan (T <= 16 only, else empty)
+    size_t Mx, K, pin;  // chunked scan (T <= 32 only, else empty)
     size_t Mx2, K2, pin2;  // its group level (many chunks only, else empty)
     size_t total;
 };
 inline MaxWorkspace max_workspace(size_t B, size_t N, size_t T) {
     MaxWorkspace w;
     size_t off = 0;
-    const size_t chunk = (size_t)scan_chunk((long long)B, (long long)N, (long long)T);
+    const size_t chunk = (size_t)scan_chunk_max((long long)B, (long long)N, (long long)T);
     w.bp = off; off += round_up(B * N * T);
     const size_t BC = lccrf::scan_supported_max((int)T) ? B * ((N + chunk - 1) / chunk) : 0;
     w.mid = off; off += round_up((BC > B ? BC : B) * 2 * T * sizeof(double));
-    w.Mx = off; off += round_up(BC * 256 * sizeof(double));
-    w.K = off; off += round_up(BC * 16);
+    const size_t TPm = (size_t)lccrf::scan_padded_tags_max((int)T);
+    w.Mx = off; off += round_up(BC * TPm * TPm * sizeof(double));
+    w.K = off; off += round_up(BC * TPm);
     w.pin = off; off += round_up(BC * sizeof(int32_t));
     const size_t C = (N + chunk - 1) / chunk;
     const size_t gs = BC ? (size_t)lccrf::scan_group_size((int)C) : 0;
     const size_t BG = gs ? B * ((C + gs - 1) / gs) : 0;
-    w.Mx2 = off; off += round_up(BG * 256 * sizeof(double));
-    w.K2 = off; off += round_up(BG * 16);
+    w.Mx2 = off; off += round_up(BG * TPm * TPm * sizeof(double));
+    w.K2 = off; off += round_up(BG * TPm);
     w.pin2 = off; off += round_up(BG * sizeof(int32_t));
     w.total = off;
     return w;
@@ -219,7 +233,11 @@ inline bool scan_pays_sum(int B, int N, int T) {
 // Longer chains pay in larger batches too: the one-wave kernels take about 0.2 us a position of the longest chain,
 // the scan 40 us + 0.75 ns a position of the batch (B=32 N=4096 805 / 140, B=16 N=16384 3193 / 239).
 inline bool scan_pays_max(int B, int N, int T) {
-    if (!lccrf::scan_supported_max(T) || N < 16 * scan_chunk(B, N, T)) return false;
+    if (!lccrf::scan_supported_max(T) || N < 16 * scan_chunk_max(B, N, T)) return false;
+    // 17 .. 32 tags: a chunk product is 32768 additions and maxima in double precision a position; the scan takes
+    // about 100 us + 4.5 ns a position of the batch against 0.33 us a position of the longest chain for the one-wave
+    // kernels (B=8 N=4096 T=32 1358 / 236, B=4 N=16384 5391 / 401)
+    if (T > 16) return (double)N * (0.33 - 0.0045 * B) > 100.0;
     return (long long)B * N <= 65536 || (double)N * (0.195 - 0.00075 * B) > 40.0;
 }
 // The entropy-like queries make two passes under the scan against one sequential pass: with 17 .. 32
@@ -300,6 +318,9 @@ inline bool lanes_pay_max(int B, int N, int T) {
 // B=128 N=512 61 / 76, B=256 N=256 41 / 75, B=128 N=2048 190 / 254, B=64 N=4096 358 / 237, B=16 N=16384 1368 / 239).
 inline bool scan_taken_max(int B, int N, int T) {
     if (!scan_pays_max(B, N, T)) return false;
+    // (17 .. 32 tags: the chain-wave kernels take 15 us + 0.133 us a position: B=8 N=4096 T=32 560 / 236,
+    // B=16 N=512 83 / 114, B=32 N=1024 153 / 212, B=1 N=8192 1098 / 189)
+    if (T > 16) return !(lanes_pay_max(B, N, T) && (double)N * (0.133 - 0.0045 * B) <= 85.0);
     return !(lanes_pay_max(B, N, T) && (double)N * (0.084 - 0.00075 * B) < 24.0);
 }
 
@@ -436,13 +457,13 @@ int lccrf_argmax_algo(const void* phi, lccrf_dtype dt, const int32_t* lengths, i
     hipError_t e;
     if (algo == LCCRF_ALGO_SCAN || (algo == LCCRF_ALGO_AUTO && scan_taken_max(B, N, T))) {
         int32_t* pin = reinterpret_cast<int32_t*>(base + w.pin);
-        e = lccrf::launch_scan_pins(dt, phi, lengths, B, N, T, scan_chunk(B, N, T), reinterpret_cast<double*>(base + w.Mx),
+        e = lccrf::launch_scan_pins(dt, phi, lengths, B, N, T, scan_chunk_max(B, N, T), reinterpret_cast<double*>(base + w.Mx),
                                     reinterpret_cast<uint8_t*>(base + w.K), pin,
                                     {reinterpret_cast<double*>(base + w.Mx2), reinterpret_cast<uint8_t*>(base + w.K2),
                                      reinterpret_cast<int32_t*>(base + w.pin2)},
                                     best_score, st);
         if (e == hipSuccess)
-            e = lccrf::launch_chunked_max(dt, phi, lengths, B, N, T, bp, mid, tags, scan_chunk(B, N, T), pin, st);
+            e = lccrf::launch_chunked_max(dt, phi, lengths, B, N, T, bp, mid, tags, scan_chunk_max(B, N, T), pin, st);
     } else {
         const bool lanes = algo == LCCRF_ALGO_SEQUENTIAL_LANES || (algo == LCCRF_ALGO_AUTO && lanes_pay_max(B, N, T));
         e = lccrf::launch_sequential_max(dt, phi, lengths, B, N, T, bp, mid, best_score, tags, st, lanes,
@@ -754,14 +775,14 @@ int lccrf_argmax_structured(const float* emit, const float* trans, const int32_t
         hipStream_t st = static_cast<hipStream_t>(stream);
         int32_t* pin = reinterpret_cast<int32_t*>(base + w.pin);
         hipError_t e = lccrf::launch_scan_pins(
-            LCCRF_F32, nullptr, lengths, B, N, T, scan_chunk(B, N, T), reinterpret_cast<double*>(base + w.Mx),
+            LCCRF_F32, nullptr, lengths, B, N, T, scan_chunk_max(B, N, T), reinterpret_cast<double*>(base + w.Mx),
             reinterpret_cast<uint8_t*>(base + w.K), pin,
             {reinterpret_cast<double*>(base + w.Mx2), reinterpret_cast<uint8_t*>(base + w.K2),
              reinterpret_cast<int32_t*>(base + w.pin2)},
             best_score, st, emit, trans);
         if (e == hipSuccess)
             e = lccrf::launch_chunked_max(LCCRF_F32, nullptr, lengths, B, N, T, reinterpret_cast<uint8_t*>(base + w.bp),
-                                          reinterpret_cast<double*>(base + w.mid), tags, scan_chunk(B, N, T), pin, st,
+                                          reinterpret_cast<double*>(base + w.mid), tags, scan_chunk_max(B, N, T), pin, st,
                                           emit, trans);
         return e == hipSuccess ? LCCRF_OK : LCCRF_ELAUNCH;
     }

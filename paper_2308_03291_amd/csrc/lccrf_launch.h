@@ -57,7 +57,8 @@ hipError_t launch_pair_marginals(int dtype, const void* phi, const int32_t* leng
 // With many chunks the serial pass over chunks is itself split into groups of scan_group_size(C) chunks
 // (0: not split); the group-level copies of the arrays above ([B][G], G = ceil(C / group size)) live in gb.
 bool scan_supported(int T);      // sum queries (T <= 32)
-bool scan_supported_max(int T);  // lccrf_argmax (T <= 16)
+bool scan_supported_max(int T);
+int scan_padded_tags_max(int T);  // 16 or 32: the side of the max-plus scan's chunk matrices  // lccrf_argmax (T <= 16)
 int scan_padded_tags(int T);     // 16 or 32: side of the stored chunk matrices
 int scan_group_size(int C);
 struct ScanGroupBuffers {

@@ -859,12 +859,12 @@ struct MaxScanArgs {
     const int32_t* lengths;
     int B, N, T;
     int chunk, C;
-    double* Mx;     // [B][C][16][16]  M_c[r][s], -inf padded
-    uint8_t* K;     // [B][C][16]      best entry tag for each exit tag
+    double* Mx;     // [B][C][TP][TP]  M_c[r][s], -inf padded (TP = 16 up to 16 tags, 32 above)
+    uint8_t* K;     // [B][C][TP]      best entry tag for each exit tag
     int32_t* pin;   // [B][C]
     float* best_score;
     // Grouped runs (GS > 0; G = ceil(C / GS) groups a sequence): group_maxplus_kernel writes the
-    // max-plus product of every group's chunk matrices to Mx2 ([B][G][16][16]); the boundary
+    // max-plus product of every group's chunk matrices to Mx2 ([B][G][TP][TP]); the boundary
     // kernel then handles one group per wave, between the tags pin_in ([B][G]) already fixed at
     // the last position of every group.
     int GS, G;
@@ -875,73 +875,177 @@ struct MaxScanArgs {
     const float* trans;
 };
 
-// A double of lane `K` of every aligned group of four lanes.
-template <int K>
-__device__ __forceinline__ double quad_read(double x) {
+// Lanes and entries of the max-plus scan's matrices: a TP x TP matrix (TP = 16 or 32) over the 64 lanes of a wave,
+// QL lanes a row, EPL consecutive entries of the row a lane.
+template <int TP>
+struct MaxScanShape {
+    static_assert(TP == 16 || TP == 32, "padded tag counts of the max-plus scan");
+    static constexpr int QL = 64 / TP;    // 4 or 2
+    static constexpr int EPL = TP / QL;   // 4 or 16
+    static constexpr int SB = TP == 16 ? 16 : 2;  // rows of a matrix read from LDS at a time (16 tags)
+};
+
+// A double of lane `K` of every aligned group of QL lanes (four: a quad; two: lanes 2n and 2n + 1).
+template <int QL, int K>
+__device__ __forceinline__ double group_read(double x) {
+    constexpr int CTRL = QL == 4 ? K * 0x55 : (K == 0 ? 0xA0 : 0xF5);  // quad_perm [K,K,K,K] / [0,0,2,2], [1,1,3,3]
     const long long bits = __double_as_longlong(x);
-    const int lo = dpp_i<K * 0x55>((int)(bits & 0xffffffffll)), hi = dpp_i<K * 0x55>((int)(bits >> 32));
+    const int lo = dpp_i<CTRL>((int)(bits & 0xffffffffll)), hi = dpp_i<CTRL>((int)(bits >> 32));
     return __longlong_as_double(((long long)hi << 32) | (unsigned int)lo);
 }
 
 // Max-plus product of matrices first .. last (none: the identity) by one wave.  Lane
-// (r = lane / 4, q = lane % 4) owns M[r][4q .. 4q+3]; row r of M is spread over the four lanes of a
-// quad and is read from their registers, the entries X_i[s][4q .. 4q+3] of every matrix, which the
-// sixteen lanes of column group q all need, go through LDS in the type XT they are stored in
-// (potentials as floats: the conversion to double is repeated by every reader, half the LDS bytes
-// are what eight such waves on a compute unit wait for).  get(slot, jj) returns this lane's four
-// entries of a matrix.  One wave per workgroup: the barrier is only the wait for the LDS writes, and
-// the two tile buffers keep the next matrix's writes off the tile that is being read.
-template <int PF, typename Slot, typename XT, typename Load, typename Get>
+// (r = lane / QL, q = lane % QL) owns M[r][EPL q .. EPL q + EPL - 1]; row r of M is spread over the QL lanes of a
+// group and is read from their registers, the entries X_i[s][EPL q ..] of every matrix, which all the
+// lanes of column group q need, go through LDS in the type XT (16 tags: potentials as floats would halve the LDS
+// bytes, doubles save every reader the conversion; 32 tags: doubles, the conversions would cost half as much again
+// as the additions and maxima).  get(slot, jj) returns this lane's entry jj of a matrix.  One wave per workgroup:
+// the barrier is only the wait for the LDS writes, and the two tile buffers keep the next matrix's writes off the
+// tile that is being read.
+template <int TP, int PF, typename Slot, typename XT, typename Load, typename Get>
 __device__ __forceinline__ void maxplus_product(int first, int last, int T, double* __restrict__ out, Load load_slot,
-                                                Get get, XT (*Xs)[16][16]) {
-    const int lane = threadIdx.x, r = lane >> 2, q = lane & 3;
+                                                Get get, XT (*Xs)[TP][TP]) {
+    using S = MaxScanShape<TP>;
+    constexpr int QL = S::QL, EPL = S::EPL, SB = S::SB;
+    const int lane = threadIdx.x, r = lane / QL, q = lane % QL;
     const double ninf = -__builtin_huge_val();
-    double M[4];
+    double M[EPL];
 #pragma unroll
-    for (int jj = 0; jj < 4; ++jj) M[jj] = (r == 4 * q + jj) ? 0.0 : ninf;
+    for (int jj = 0; jj < EPL; ++jj) M[jj] = (r == EPL * q + jj) ? 0.0 : ninf;
     Slot ring[PF];
     auto load = [&](int i, int slot) { load_slot(i, ring[slot]); };
     int buf = 0;
     walk<PF>(first, last, +1, load, [&](int, int slot) {
         buf ^= 1;
-        XT(*X)[16] = Xs[buf];
+        XT(*X)[TP] = Xs[buf];
 #pragma unroll
-        for (int jj = 0; jj < 4; ++jj) X[r][4 * q + jj] = get(ring[slot], jj);
+        for (int jj = 0; jj < EPL; ++jj) X[r][EPL * q + jj] = get(ring[slot], jj);
         __syncthreads();
-        // all sixteen rows of this lane's four columns first (left to itself the compiler waits for every LDS
-        // read before it issues the next: sixteen to thirty-two latencies a position), then the arithmetic
-        XT xr[16][4];
+        double best[EPL];
 #pragma unroll
-        for (int s = 0; s < 16; ++s)
+        for (int jj = 0; jj < EPL; ++jj) best[jj] = ninf;
+        // SB rows of this lane's columns at a time, all their reads first (left to itself the compiler waits for
+        // every LDS read before it issues the next), then the arithmetic; row s of M's row r is entry s % EPL of
+        // lane s / EPL of the group
 #pragma unroll
-            for (int jj = 0; jj < 4; ++jj) xr[s][jj] = X[s][4 * q + jj];
-        __builtin_amdgcn_sched_barrier(0);
-        double best[4] = {ninf, ninf, ninf, ninf};
-        const auto row = [&](int s, double m) {
+        for (int s0 = 0; s0 < TP; s0 += SB) {
+            XT xr[SB][EPL];
 #pragma unroll
-            for (int jj = 0; jj < 4; ++jj) best[jj] = fmax(best[jj], m + (double)xr[s][jj]);
-        };
+            for (int s = 0; s < SB; ++s)
 #pragma unroll
-        for (int jj = 0; jj < 4; ++jj) {
-            row(jj, quad_read<0>(M[jj]));
-            row(4 + jj, quad_read<1>(M[jj]));
-            row(8 + jj, quad_read<2>(M[jj]));
-            row(12 + jj, quad_read<3>(M[jj]));
+                for (int jj = 0; jj < EPL; ++jj) xr[s][jj] = X[s0 + s][EPL * q + jj];
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int s = 0; s < SB; ++s) {
+                constexpr int kNone = 0;
+                (void)kNone;
+                const int sg = s0 + s;
+                double m;
+                if constexpr (QL == 4) {
+                    const int k = sg / EPL;
+                    m = k == 0 ? group_read<4, 0>(M[sg % EPL]) : k == 1 ? group_read<4, 1>(M[sg % EPL])
+                        : k == 2 ? group_read<4, 2>(M[sg % EPL]) : group_read<4, 3>(M[sg % EPL]);
+                } else {
+                    m = sg / EPL == 0 ? group_read<2, 0>(M[sg % EPL]) : group_read<2, 1>(M[sg % EPL]);
+                }
+#pragma unroll
+                for (int jj = 0; jj < EPL; ++jj) best[jj] = fmax(best[jj], m + (double)xr[s][jj]);
+            }
         }
 #pragma unroll
-        for (int jj = 0; jj < 4; ++jj) M[jj] = best[jj];
+        for (int jj = 0; jj < EPL; ++jj) M[jj] = best[jj];
     });
 #pragma unroll
-    for (int jj = 0; jj < 4; ++jj) out[r * 16 + 4 * q + jj] = (r < T && 4 * q + jj < T) ? M[jj] : ninf;
+    for (int jj = 0; jj < EPL; ++jj) out[r * TP + EPL * q + jj] = (r < T && EPL * q + jj < T) ? M[jj] : ninf;
 }
 
-struct MaxSlotF { float x[4]; };
-struct MaxSlotD { double x[4]; };
+// The same product for 17 .. 32 tags (32 x 32 matrices, 1024 candidates a position and lane pair).  Lane (a = lane / 8,
+// b = lane % 8) owns the 4 x 4 block M[4a .. 4a+3][4b .. 4b+3]: for a source tag s it needs four entries of column s
+// of M and four of row s of X, 48 or 64 bytes of LDS for sixteen candidates (a lane that owned part of a row, as
+// above, would read 136 bytes for thirty-two, and the product was bound by LDS bandwidth at five times the cost of
+// its arithmetic).  M goes through LDS transposed (Mt[s][r]), X (X[s][t]) in the type XT it is given in (potentials as floats,
+// chunk products as doubles); the loop over source tags stays a loop (unrolled, a position kept a thousand values
+// in flight and spilled), with the reads of the next source tag issued before the arithmetic of the current one.
+// get(slot, i, j): entry (4a + i, 4b + j) of a matrix.
+template <int PF, typename Slot, typename XT, typename Load, typename Get>
+__device__ __forceinline__ void maxplus_product32(int first, int last, int T, double* __restrict__ out, Load load_slot,
+                                                  Get get, XT (*Xs)[32][32], double (*Mt)[32]) {
+    const int lane = threadIdx.x, a4 = 4 * (lane >> 3), b4 = 4 * (lane & 7);
+    const double ninf = -__builtin_huge_val();
+    double M[4][4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) M[i][j] = (a4 + i == b4 + j) ? 0.0 : ninf;
+    Slot ring[PF];
+    auto load = [&](int i, int slot) { load_slot(i, ring[slot]); };
+    int buf = 0;
+    walk<PF>(first, last, +1, load, [&](int, int slot) {
+        buf ^= 1;
+        XT(*X)[32] = Xs[buf];  // (two tiles: the writes of a position need not wait behind the reads of the one before)
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) X[a4 + i][b4 + j] = get(ring[slot], i, j);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            double2 lo, hi;
+            lo.x = M[0][j]; lo.y = M[1][j]; hi.x = M[2][j]; hi.y = M[3][j];
+            *reinterpret_cast<double2*>(&Mt[b4 + j][a4]) = lo;
+            *reinterpret_cast<double2*>(&Mt[b4 + j][a4 + 2]) = hi;
+        }
+        __syncthreads();
+        double best[4][4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) best[i][j] = ninf;
+        const auto read = [&](int sg, double (&m)[4], XT (&x)[4]) {
+            const double2 lo = *reinterpret_cast<const double2*>(&Mt[sg][a4]);
+            const double2 hi = *reinterpret_cast<const double2*>(&Mt[sg][a4 + 2]);
+            m[0] = lo.x; m[1] = lo.y; m[2] = hi.x; m[3] = hi.y;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) x[j] = X[sg][b4 + j];
+        };
+        const auto fold = [&](const double (&m)[4], const XT (&x)[4]) {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const double xj = (double)x[j];
+#pragma unroll
+                for (int i = 0; i < 4; ++i) best[i][j] = fmax(best[i][j], m[i] + xj);
+            }
+        };
+        double ma[4], mb[4];
+        XT xa[4], xb[4];
+        read(0, ma, xa);
+#pragma unroll 2
+        for (int sg = 0; sg < 32; sg += 2) {
+            read(sg + 1, mb, xb);
+            fold(ma, xa);
+            read(sg + 2 < 32 ? sg + 2 : 31, ma, xa);
+            fold(mb, xb);
+        }
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) M[i][j] = best[i][j];
+    });
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) out[(a4 + i) * 32 + b4 + j] = (a4 + i < T && b4 + j < T) ? M[i][j] : ninf;
+}
 
+struct MaxBlockF { float x[4][4]; };
+struct MaxBlockD { double x[4][4]; };
+struct MaxBlockE { float e[4]; };
+
+// Phase A at 17 .. 32 tags.
 template <typename TIN, bool STRUCT = false>
-__global__ __launch_bounds__(64) void chunk_maxplus_kernel(MaxScanArgs a) {
-    __shared__ __attribute__((aligned(16))) double Xs[2][16][16];
-    const int lane = threadIdx.x, r = lane >> 2, q = lane & 3;
+__global__ __launch_bounds__(64) void chunk_maxplus32_kernel(MaxScanArgs a) {
+    __shared__ __attribute__((aligned(16))) float Xs[2][32][32];
+    __shared__ __attribute__((aligned(16))) double Mt[32][32];
+    const int lane = threadIdx.x, a4 = 4 * (lane >> 3), b4 = 4 * (lane & 7);
     const int b = blockIdx.x / a.C, c = blockIdx.x % a.C;
     const int T = a.T, N = a.N;
     const int L = clamp_length(a.lengths, b, N);
@@ -949,63 +1053,144 @@ __global__ __launch_bounds__(64) void chunk_maxplus_kernel(MaxScanArgs a) {
     int first, last;
     chunk_range(c, a.chunk, L, first, last);
     const size_t TT = (size_t)T * T;
-    int off[4];
-    bool in[4];
+    int off[4][4];
+    unsigned in = 0;
 #pragma unroll
-    for (int jj = 0; jj < 4; ++jj) {
-        const int t = 4 * q + jj;
-        in[jj] = r < T && t < T;
-        off[jj] = (r < T ? r : T - 1) * T + (t < T ? t : T - 1);
-    }
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int r = a4 + i, t = b4 + j;
+            in |= (r < T && t < T) ? (1u << (4 * i + j)) : 0u;
+            off[i][j] = (r < T ? r : T - 1) * T + (t < T ? t : T - 1);
+        }
+    double* out = a.Mx + ((size_t)b * a.C + c) * 1024;
     if constexpr (STRUCT) {
         // the candidates are the single-precision sums trans + emit, as the materialised tensor would hold them
         const float* emb = a.emit + (size_t)b * N * T;
-        float tr[4];
-        int col[4];
+        float tr[4][4];
 #pragma unroll
-        for (int jj = 0; jj < 4; ++jj) {
-            tr[jj] = a.trans[off[jj]];
-            col[jj] = 4 * q + jj < T ? 4 * q + jj : T - 1;
-        }
-        maxplus_product<kScanPF, MaxSlotF, double>(
-            first, last, T, a.Mx + ((size_t)b * a.C + c) * 256,
-            [&](int i, MaxSlotF& sl) {
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) tr[i][j] = a.trans[off[i][j]];
+        maxplus_product32<3, MaxBlockE, float>(
+            first, last, T, out,
+            [&](int i, MaxBlockE& sl) {
                 const float* m = emb + (size_t)i * T;
 #pragma unroll
-                for (int jj = 0; jj < 4; ++jj) sl.x[jj] = m[col[jj]];
+                for (int j = 0; j < 4; ++j) sl.e[j] = m[b4 + j < T ? b4 + j : T - 1];
             },
-            [&](const MaxSlotF& sl, int jj) { return (double)(in[jj] ? tr[jj] + sl.x[jj] : LCCRF_NEG_INF); }, Xs);
+            [&](const MaxBlockE& sl, int i, int j) { return (in >> (4 * i + j)) & 1 ? tr[i][j] + sl.e[j] : LCCRF_NEG_INF; }, Xs, Mt);
         return;
     }
     const TIN* phib = static_cast<const TIN*>(a.phi) + (size_t)b * N * TT;
-    maxplus_product<kScanPF, MaxSlotF, double>(
-        first, last, T, a.Mx + ((size_t)b * a.C + c) * 256,
-        [&](int i, MaxSlotF& sl) {
+    maxplus_product32<3, MaxBlockF, float>(
+        first, last, T, out,
+        [&](int i, MaxBlockF& sl) {
             const TIN* m = phib + (size_t)i * TT;
 #pragma unroll
-            for (int jj = 0; jj < 4; ++jj) sl.x[jj] = Elem<TIN>::get(m + off[jj]);
+            for (int ii = 0; ii < 4; ++ii)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) sl.x[ii][j] = Elem<TIN>::get(m + off[ii][j]);
         },
-        [&](const MaxSlotF& sl, int jj) { return (double)(in[jj] ? sl.x[jj] : LCCRF_NEG_INF); }, Xs);
+        [&](const MaxBlockF& sl, int i, int j) { return (in >> (4 * i + j)) & 1 ? sl.x[i][j] : LCCRF_NEG_INF; }, Xs, Mt);
 }
 
-// One wave per group of GS chunks: the max-plus product of the group's chunk matrices.
-__global__ __launch_bounds__(64) void group_maxplus_kernel(MaxScanArgs a) {
-    __shared__ __attribute__((aligned(16))) double Xs[2][16][16];
-    const int lane = threadIdx.x, r = lane >> 2, q = lane & 3;
+// One wave per group of GS chunks at 17 .. 32 tags.
+__global__ __launch_bounds__(64) void group_maxplus32_kernel(MaxScanArgs a) {
+    __shared__ __attribute__((aligned(16))) double Xs[2][32][32];
+    __shared__ __attribute__((aligned(16))) double Mt[32][32];
+    const int lane = threadIdx.x, a4 = 4 * (lane >> 3), b4 = 4 * (lane & 7);
     const int b = blockIdx.x / a.G, g = blockIdx.x % a.G;
     const int L = clamp_length(a.lengths, b, a.N);
     const int Cb = (L + a.chunk - 1) / a.chunk;
     const int c0 = g * a.GS;
     if (c0 >= Cb) return;
     const int c1 = (c0 + a.GS < Cb ? c0 + a.GS : Cb) - 1;
-    const double* Mb = a.Mx + (size_t)b * a.C * 256 + r * 16 + 4 * q;
-    maxplus_product<4, MaxSlotD, double>(
-        c0, c1, a.T, a.Mx2 + ((size_t)b * a.G + g) * 256,
-        [&](int c, MaxSlotD& sl) {
+    const double* Mb = a.Mx + (size_t)b * a.C * 1024 + a4 * 32 + b4;
+    maxplus_product32<2, MaxBlockD, double>(
+        c0, c1, a.T, a.Mx2 + ((size_t)b * a.G + g) * 1024,
+        [&](int c, MaxBlockD& sl) {
 #pragma unroll
-            for (int jj = 0; jj < 4; ++jj) sl.x[jj] = Mb[(size_t)c * 256 + jj];
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) sl.x[i][j] = Mb[(size_t)c * 1024 + i * 32 + j];
         },
-        [&](const MaxSlotD& sl, int jj) { return sl.x[jj]; }, Xs);
+        [&](const MaxBlockD& sl, int i, int j) { return sl.x[i][j]; }, Xs, Mt);
+}
+
+template <int EPL> struct MaxSlotF { float x[EPL]; };
+template <int EPL> struct MaxSlotD { double x[EPL]; };
+
+template <int TP, typename TIN, bool STRUCT = false>
+__global__ __launch_bounds__(64) void chunk_maxplus_kernel(MaxScanArgs a) {
+    using S = MaxScanShape<TP>;
+    constexpr int QL = S::QL, EPL = S::EPL, PF = TP == 16 ? kScanPF : 3;
+    __shared__ __attribute__((aligned(16))) double Xs[2][TP][TP];
+    const int lane = threadIdx.x, r = lane / QL, q = lane % QL;
+    const int b = blockIdx.x / a.C, c = blockIdx.x % a.C;
+    const int T = a.T, N = a.N;
+    const int L = clamp_length(a.lengths, b, N);
+    if (c * a.chunk >= L) return;
+    int first, last;
+    chunk_range(c, a.chunk, L, first, last);
+    const size_t TT = (size_t)T * T;
+    int off[EPL];
+    unsigned in = 0;
+#pragma unroll
+    for (int jj = 0; jj < EPL; ++jj) {
+        const int t = EPL * q + jj;
+        in |= (r < T && t < T) ? (1u << jj) : 0u;
+        off[jj] = (r < T ? r : T - 1) * T + (t < T ? t : T - 1);
+    }
+    if constexpr (STRUCT) {
+        // the candidates are the single-precision sums trans + emit, as the materialised tensor would hold them
+        const float* emb = a.emit + (size_t)b * N * T;
+        float tr[EPL];
+#pragma unroll
+        for (int jj = 0; jj < EPL; ++jj) tr[jj] = a.trans[off[jj]];
+        const int col0 = EPL * q;
+        maxplus_product<TP, PF, MaxSlotF<EPL>, double>(
+            first, last, T, a.Mx + ((size_t)b * a.C + c) * (TP * TP),
+            [&](int i, MaxSlotF<EPL>& sl) {
+                const float* m = emb + (size_t)i * T;
+#pragma unroll
+                for (int jj = 0; jj < EPL; ++jj) sl.x[jj] = m[col0 + jj < T ? col0 + jj : T - 1];
+            },
+            [&](const MaxSlotF<EPL>& sl, int jj) { return (double)((in >> jj) & 1 ? tr[jj] + sl.x[jj] : LCCRF_NEG_INF); }, Xs);
+        return;
+    }
+    const TIN* phib = static_cast<const TIN*>(a.phi) + (size_t)b * N * TT;
+    maxplus_product<TP, PF, MaxSlotF<EPL>, double>(
+        first, last, T, a.Mx + ((size_t)b * a.C + c) * (TP * TP),
+        [&](int i, MaxSlotF<EPL>& sl) {
+            const TIN* m = phib + (size_t)i * TT;
+#pragma unroll
+            for (int jj = 0; jj < EPL; ++jj) sl.x[jj] = Elem<TIN>::get(m + off[jj]);
+        },
+        [&](const MaxSlotF<EPL>& sl, int jj) { return (double)((in >> jj) & 1 ? sl.x[jj] : LCCRF_NEG_INF); }, Xs);
+}
+
+// One wave per group of GS chunks: the max-plus product of the group's chunk matrices.
+template <int TP>
+__global__ __launch_bounds__(64) void group_maxplus_kernel(MaxScanArgs a) {
+    using S = MaxScanShape<TP>;
+    constexpr int QL = S::QL, EPL = S::EPL;
+    __shared__ __attribute__((aligned(16))) double Xs[2][TP][TP];
+    const int lane = threadIdx.x, r = lane / QL, q = lane % QL;
+    const int b = blockIdx.x / a.G, g = blockIdx.x % a.G;
+    const int L = clamp_length(a.lengths, b, a.N);
+    const int Cb = (L + a.chunk - 1) / a.chunk;
+    const int c0 = g * a.GS;
+    if (c0 >= Cb) return;
+    const int c1 = (c0 + a.GS < Cb ? c0 + a.GS : Cb) - 1;
+    const double* Mb = a.Mx + (size_t)b * a.C * (TP * TP) + r * TP + EPL * q;
+    maxplus_product<TP, (TP == 16 ? 4 : 2), MaxSlotD<EPL>, double>(
+        c0, c1, a.T, a.Mx2 + ((size_t)b * a.G + g) * (TP * TP),
+        [&](int c, MaxSlotD<EPL>& sl) {
+#pragma unroll
+            for (int jj = 0; jj < EPL; ++jj) sl.x[jj] = Mb[(size_t)c * (TP * TP) + jj];
+        },
+        [&](const MaxSlotD<EPL>& sl, int jj) { return sl.x[jj]; }, Xs);
 }
 
 constexpr int kPinWindow = 1024;  // chunks of back-pointers held in LDS at a time by the back-trace
@@ -1016,10 +1201,13 @@ constexpr int kPinWindow = 1024;  // chunks of back-pointers held in LDS at a ti
 // sequence starts from delta_0 and ends in its best final tag; a group starts from the tag
 // already fixed at the end of the group before it (group 0: delta_0) and ends in the tag fixed at
 // its own end, so what it finds is a best path between those two tags.
-template <typename TIN>
+// (Exit tag t in lanes QL t .. QL t + QL - 1, lane q of them taking the entry tags EPL q .. EPL q + EPL - 1.)
+template <int TP, typename TIN>
 __global__ __launch_bounds__(64) void chunk_maxplus_boundary_kernel(MaxScanArgs a) {
-    __shared__ uint8_t win[kPinWindow * 16];
-    const int lane = threadIdx.x, t = lane >> 2, q = lane & 3;
+    using S = MaxScanShape<TP>;
+    constexpr int QL = S::QL, EPL = S::EPL, PF = TP == 16 ? kScanPF : 3;
+    __shared__ uint8_t win[kPinWindow * TP];
+    const int lane = threadIdx.x, t = lane / QL, q = lane % QL;
     const bool grouped = a.GS > 0;
     const int b = grouped ? blockIdx.x / a.G : blockIdx.x, g = grouped ? blockIdx.x % a.G : 0;
     const int T = a.T, N = a.N;
@@ -1043,35 +1231,35 @@ __global__ __launch_bounds__(64) void chunk_maxplus_boundary_kernel(MaxScanArgs 
     } else {
         dv = (t == a.pin_in[bg + g - 1]) ? 0.0 : ninf;  // the tag fixed at the end of the group before
     }
-    double mm[kScanPF][4];
+    double mm[PF][EPL];
     auto load = [&](int c, int slot) {
-        const double* M = a.Mx + (cb + c) * 256;
+        const double* M = a.Mx + (cb + c) * (TP * TP);
 #pragma unroll
-        for (int jj = 0; jj < 4; ++jj) mm[slot][jj] = M[(4 * q + jj) * 16 + t];
+        for (int jj = 0; jj < EPL; ++jj) mm[slot][jj] = M[(EPL * q + jj) * TP + t];
     };
-    walk<kScanPF>(c0, c1, +1, load, [&](int c, int slot) {
+    walk<PF>(c0, c1, +1, load, [&](int c, int slot) {
         double bv = ninf;
         int ba = 0x7fffffff;
-        double in[4];
+        double in[EPL];
 #pragma unroll
-        for (int jj = 0; jj < 4; ++jj) in[jj] = __shfl(dv, 16 * q + 4 * jj, 64);
+        for (int jj = 0; jj < EPL; ++jj) in[jj] = __shfl(dv, QL * (EPL * q + jj), 64);
 #pragma unroll
-        for (int jj = 0; jj < 4; ++jj) {  // ascending entry tags: the first maximum wins
+        for (int jj = 0; jj < EPL; ++jj) {  // ascending entry tags: the first maximum wins
             const double val = in[jj] + mm[slot][jj];
-            if (val > bv) { bv = val; ba = 4 * q + jj; }
+            if (val > bv) { bv = val; ba = EPL * q + jj; }
         }
 #pragma unroll
-        for (int off = 1; off < 4; off <<= 1) {
+        for (int off = 1; off < QL; off <<= 1) {
             const double pv = __shfl_xor(bv, off, 64);
             const int pa = __shfl_xor(ba, off, 64);
             if (pv > bv || (pv == bv && pa < ba)) { bv = pv; ba = pa; }
         }
         dv = bv;
-        if (q == 0) a.K[(cb + c) * 16 + t] = (uint8_t)(ba == 0x7fffffff ? 0 : ba);
+        if (q == 0) a.K[(cb + c) * TP + t] = (uint8_t)(ba == 0x7fffffff ? 0 : ba);
     });
     int y;
     if (!grouped) {
-        // best tag at the last position: first maximum (entry t sits in lanes 4t .. 4t+3)
+        // best tag at the last position: first maximum (entry t sits in lanes QL t .. QL t + QL - 1)
         double bv = (q == 0 && t < T) ? dv : ninf;
         int ba = (q == 0 && t < T) ? t : 0x7fffffff;
 #pragma unroll
@@ -1095,13 +1283,13 @@ __global__ __launch_bounds__(64) void chunk_maxplus_boundary_kernel(MaxScanArgs 
     if (lane == 0) a.pin[cb + c1] = y;
     while (hi > c0 + 1) {
         const int lo = (hi - kPinWindow > c0 + 1) ? hi - kPinWindow : c0 + 1;
-        const int nbytes = (hi - lo) * 16;
-        const uint8_t* src = a.K + (cb + lo) * 16;
+        const int nbytes = (hi - lo) * TP;
+        const uint8_t* src = a.K + (cb + lo) * TP;
         for (int k = lane; k < nbytes; k += 64) win[k] = src[k];
         __syncthreads();
         if (lane == 0) {
             for (int c = hi - 1; c >= lo; --c) {
-                y = win[(c - lo) * 16 + y];
+                y = win[(c - lo) * TP + y];
                 a.pin[cb + c - 1] = y;
             }
         }
@@ -1111,9 +1299,10 @@ __global__ __launch_bounds__(64) void chunk_maxplus_boundary_kernel(MaxScanArgs 
 }
 
 // ---------------------------------------------------------------------------------------
-// Sum queries: tag sets up to 64 (matrices in 1, 4, 9 or 16 blocks of 16 x 16); the max-plus scan: up to 16.
+// Sum queries: tag sets up to 64 (matrices in 1, 4, 9 or 16 blocks of 16 x 16); the max-plus scan: up to 32.
 bool scan_supported(int T) { return T >= 1 && T <= 64; }
-bool scan_supported_max(int T) { return T >= 1 && T <= 16; }
+bool scan_supported_max(int T) { return T >= 1 && T <= 32; }
+int scan_padded_tags_max(int T) { return T <= 16 ? 16 : 32; }
 int scan_padded_tags(int T) { return (T + 15) / 16 * 16; }
 
 // Chunks per group when phase B is itself run as a scan; 0: one serial pass over all chunks.  The
@@ -1185,31 +1374,37 @@ hipError_t launch_scan_boundaries(int dtype, const void* phi, const int32_t* len
 }
 
 
-template <typename TIN>
+template <int TP, typename TIN>
 static hipError_t launch_scan_pins_t(MaxScanArgs a, const MaxGroupBuffers& gb, hipStream_t st) {
-    if (a.emit) hipLaunchKernelGGL((chunk_maxplus_kernel<float, true>), dim3(a.B * a.C), dim3(64), 0, st, a);
-    else hipLaunchKernelGGL(chunk_maxplus_kernel<TIN>, dim3(a.B * a.C), dim3(64), 0, st, a);
+    if constexpr (TP == 32) {
+        if (a.emit) hipLaunchKernelGGL((chunk_maxplus32_kernel<float, true>), dim3(a.B * a.C), dim3(64), 0, st, a);
+        else hipLaunchKernelGGL((chunk_maxplus32_kernel<TIN>), dim3(a.B * a.C), dim3(64), 0, st, a);
+    } else {
+        if (a.emit) hipLaunchKernelGGL((chunk_maxplus_kernel<TP, float, true>), dim3(a.B * a.C), dim3(64), 0, st, a);
+        else hipLaunchKernelGGL((chunk_maxplus_kernel<TP, TIN>), dim3(a.B * a.C), dim3(64), 0, st, a);
+    }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     const int gs = scan_group_size(a.C);
     if (gs == 0) {
-        hipLaunchKernelGGL(chunk_maxplus_boundary_kernel<TIN>, dim3(a.B), dim3(64), 0, st, a);
+        hipLaunchKernelGGL((chunk_maxplus_boundary_kernel<TP, TIN>), dim3(a.B), dim3(64), 0, st, a);
         return hipGetLastError();
     }
     const int G = (a.C + gs - 1) / gs;
     MaxScanArgs p = a;
     p.GS = gs; p.G = G; p.Mx2 = gb.Mx2;
-    hipLaunchKernelGGL(group_maxplus_kernel, dim3(a.B * G), dim3(64), 0, st, p);
+    if constexpr (TP == 32) hipLaunchKernelGGL(group_maxplus32_kernel, dim3(a.B * G), dim3(64), 0, st, p);
+    else hipLaunchKernelGGL(group_maxplus_kernel<TP>, dim3(a.B * G), dim3(64), 0, st, p);
     if ((e = hipGetLastError()) != hipSuccess) return e;
     // phase B over the groups: the same kernel, a group in the place of a chunk (best score, tags at group ends)
     MaxScanArgs u = a;
     u.chunk = a.chunk * gs; u.C = G; u.Mx = gb.Mx2; u.K = gb.K2; u.pin = gb.pin2;
-    hipLaunchKernelGGL(chunk_maxplus_boundary_kernel<TIN>, dim3(a.B), dim3(64), 0, st, u);
+    hipLaunchKernelGGL((chunk_maxplus_boundary_kernel<TP, TIN>), dim3(a.B), dim3(64), 0, st, u);
     if ((e = hipGetLastError()) != hipSuccess) return e;
     // ... and inside every group at once, between the tags just fixed
     MaxScanArgs l = a;
     l.GS = gs; l.G = G; l.best_score = nullptr; l.pin_in = gb.pin2;
-    hipLaunchKernelGGL(chunk_maxplus_boundary_kernel<TIN>, dim3(a.B * G), dim3(64), 0, st, l);
+    hipLaunchKernelGGL((chunk_maxplus_boundary_kernel<TP, TIN>), dim3(a.B * G), dim3(64), 0, st, l);
     return hipGetLastError();
 }
 
@@ -1219,7 +1414,9 @@ hipError_t launch_scan_pins(int dtype, const void* phi, const int32_t* lengths, 
     const int C = (N + chunk - 1) / chunk;
     MaxScanArgs a{phi, lengths, B, N, T, chunk, C, Mx, K, pin, best_score, 0, 1, nullptr, nullptr, emit, trans};
     if (emit && (dtype != 0 || !trans)) return hipErrorInvalidValue;
-    return dtype == 0 ? launch_scan_pins_t<float>(a, gb, st) : launch_scan_pins_t<uint16_t>(a, gb, st);
+    if (!scan_supported_max(T)) return hipErrorInvalidValue;
+    if (T <= 16) return dtype == 0 ? launch_scan_pins_t<16, float>(a, gb, st) : launch_scan_pins_t<16, uint16_t>(a, gb, st);
+    return dtype == 0 ? launch_scan_pins_t<32, float>(a, gb, st) : launch_scan_pins_t<32, uint16_t>(a, gb, st);
 }
 
 }  // namespace lccrf

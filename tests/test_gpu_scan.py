@@ -6,11 +6,12 @@ import pytest
 import torch
 
 from paper_2308_03291_amd import workloads
-from test_gpu_parity import check_case, crf  # noqa: F401  (fixture)
+from test_gpu_parity import _path_score, check_case, crf  # noqa: F401  (fixture)
 
 pytestmark = pytest.mark.gpu
 
-SUMS = ("logz", "mu")   # the scan of the max-plus semiring stops at 16 tags
+SUMS = ("logz", "mu")   # the scan of the max-plus semiring stops at 32 tags
+ALL = ("logz", "mu", "vit")
 
 
 @pytest.fixture
@@ -122,6 +123,41 @@ def test_scan_viterbi_matches_sequential_path(crf):
     assert torch.allclose(s_a, s_b, rtol=1e-6, atol=0)
 
 
+@pytest.mark.parametrize("T,N,k", [(17, 900, 0), (24, 2100, 8), (32, 3000, 0), (32, 1500, 4), (29, 700, 32)])
+def test_scan_viterbi_17_to_32_tags_matches_sequential_path(crf, chunk, T, N, k):
+    """The max-plus scan at 17 .. 32 tags (chunk products of 32 x 32 matrices in double precision, a 4 x 4 block a
+    lane; with 64 chunks or more a sequence the boundary phase runs over groups of chunks): the path and the score of
+    the sequential schedule (float32), a path of the best score (bfloat16, where exact ties occur)."""
+    chunk(k)
+    for dtype in ("f32", "bf16"):
+        phi, lens = workloads.random_case(5670 + T, 4, N, T, scale=2.0, ragged=True, min_len=1, dtype=dtype)
+        dphi, dl = phi.cuda(), lens.cuda()
+        s_a, y_a = crf.lccrf_argmax(dphi, dl, algo=crf.ALGO_SCAN)
+        s_b, y_b = crf.lccrf_argmax(dphi, dl, algo=crf.ALGO_SEQUENTIAL)
+        assert torch.equal(s_a, s_b), dtype
+        if dtype == "f32":      # generic potentials: a unique best path
+            assert torch.equal(y_a, y_b)
+        else:                   # bfloat16 potentials tie exactly now and then: any path with the best score
+            phi64 = phi.to(torch.float32).numpy().astype(np.float64)
+            for b_ in range(phi.shape[0]):
+                L = int(lens[b_])
+                y = y_a[b_, :L].cpu().numpy()
+                assert (y_a[b_, L:] == -1).all() and ((y >= 0) & (y < T)).all()
+                got = _path_score(phi64[b_], y, L)
+                assert abs(got - float(s_a[b_])) <= 1e-5 * max(1.0, abs(got))
+
+
+def test_auto_takes_the_max_plus_scan_on_long_chains_of_17_to_32_tags(crf):
+    A = lambda B, N, T: crf.auto_algo(crf.OP_ARGMAX, B, N, T)
+    assert A(8, 4096, 32) == crf.ALGO_SCAN
+    assert A(1, 8192, 24) == crf.ALGO_SCAN
+    assert A(4, 16384, 17) == crf.ALGO_SCAN
+    assert A(32, 1024, 32) == crf.ALGO_SEQUENTIAL_LANES
+    assert A(16, 512, 32) == crf.ALGO_SEQUENTIAL_LANES
+    assert A(128, 256, 32) == crf.ALGO_SEQUENTIAL_LANES       # the paper's shape
+    assert A(8, 4096, 33) == crf.ALGO_SEQUENTIAL_LANES        # no max-plus scan above 32 tags
+
+
 def test_scan_viterbi_many_chunks_cross_the_trace_window(crf, chunk):
     """More chunks than one window of the chunk-level back-trace holds."""
     chunk(4)
@@ -148,14 +184,14 @@ def test_scan_up_to_32_tags(crf, oracle_mod, chunk, T, N, k):
     chunk(k)
     lens = _lens_around_chunks(N, k)
     phi, _ = workloads.random_case(5900 + 31 * T + N, len(lens), N, T, scale=1.5)
-    check_case(crf, oracle_mod, phi, lens, algo=crf.ALGO_SCAN, what=f"scan T={T} N={N} k={k}", queries=SUMS)
+    check_case(crf, oracle_mod, phi, lens, algo=crf.ALGO_SCAN, what=f"scan T={T} N={N} k={k}", queries=ALL)
 
 
 def test_scan_32_tags_bf16_forbidden_edges_jumps_and_offsets(crf, oracle_mod, chunk):
     chunk(16)
     T, N = 32, 200
     phi, lens = workloads.random_case(5910, 5, N, T, scale=3.0, ragged=True, min_len=3, dtype="bf16")
-    check_case(crf, oracle_mod, phi, lens, poison=False, algo=crf.ALGO_SCAN, what="scan T=32 bf16", queries=SUMS)
+    check_case(crf, oracle_mod, phi, lens, poison=False, algo=crf.ALGO_SCAN, what="scan T=32 bf16", queries=ALL)
     chunk(8)
     T, N = 29, 50
     phi, _ = workloads.random_case(5920, 5, N, T)
@@ -167,7 +203,7 @@ def test_scan_32_tags_bf16_forbidden_edges_jumps_and_offsets(crf, oracle_mod, ch
     phi[3][mask] = ninf
     phi[3, :, torch.arange(T), torch.arange(T)] = 0.0
     lens = torch.tensor([50, 50, 50, 50, 33], dtype=torch.int32)
-    check_case(crf, oracle_mod, phi, lens, poison=False, algo=crf.ALGO_SCAN, what="scan T=29 -inf", queries=SUMS)
+    check_case(crf, oracle_mod, phi, lens, poison=False, algo=crf.ALGO_SCAN, what="scan T=29 -inf", queries=ALL)
     T, N = 32, 70
     phi, lens = workloads.random_case(5930, 4, N, T, scale=1.0, ragged=True, min_len=N // 2)
     g = torch.Generator().manual_seed(17)
@@ -175,10 +211,10 @@ def test_scan_32_tags_bf16_forbidden_edges_jumps_and_offsets(crf, oracle_mod, ch
     wide = torch.randint(0, 2, (4, N, T, T), generator=g).to(torch.float32) * -150.0
     wide[:, ::3] = 0.0
     check_case(crf, oracle_mod, (phi + jump + wide).contiguous(), lens, algo=crf.ALGO_SCAN, what="scan T=32 jumps",
-               queries=SUMS)
+               queries=ALL)
     chunk(16)
     phi, lens = workloads.random_case(5940, 3, 120, 24, scale=1.0, ragged=True, min_len=60)
-    check_case(crf, oracle_mod, (phi + 40.0).contiguous(), lens, algo=crf.ALGO_SCAN, what="scan T=24 offsets", queries=SUMS)
+    check_case(crf, oracle_mod, (phi + 40.0).contiguous(), lens, algo=crf.ALGO_SCAN, what="scan T=24 offsets", queries=ALL)
 
 
 @pytest.mark.parametrize("scale", [5.0, 8.0, 10.0, 12.0])
@@ -189,7 +225,7 @@ def test_scan_32_tags_precision_ladder(crf, oracle_mod, chunk, T, scale):
     chunks, so that some chunks give up late and others never, and group products above them."""
     chunk(32)
     phi, lens = workloads.random_case(5950 + T, 3, 2100, T, scale=scale, ragged=True, min_len=1500)
-    check_case(crf, oracle_mod, phi, lens, algo=crf.ALGO_SCAN, what=f"scan T={T} scale {scale}", queries=SUMS)
+    check_case(crf, oracle_mod, phi, lens, algo=crf.ALGO_SCAN, what=f"scan T={T} scale {scale}", queries=ALL)
 
 
 def test_scan_32_tags_agrees_with_sequential_on_the_paper_shape(crf):
@@ -273,7 +309,7 @@ def test_scan_needs_a_small_tag_set(crf):
     phi, _ = workloads.random_case(5800, 2, 8, 65)
     with pytest.raises(crf.LccrfError, match="not available"):
         crf.lccrf_marginals(phi.cuda(), None, algo=crf.ALGO_SCAN)
-    phi, _ = workloads.random_case(5801, 2, 8, 17)
+    phi, _ = workloads.random_case(5801, 2, 8, 33)
     with pytest.raises(crf.LccrfError, match="not available"):
         crf.lccrf_argmax(phi.cuda(), None, algo=crf.ALGO_SCAN)
     with pytest.raises(crf.LccrfError, match="invalid argument"):

@@ -219,6 +219,22 @@ def test_structured_scan_many_chunks(crf, oracle_mod, chunk, T, N, k):
     _check(crf, oracle_mod, emit, trans, lens, f"structured scan, many chunks, T={T} N={N} k={k}")
 
 
+@pytest.mark.parametrize("T,N", [(17, 1500), (32, 2000), (27, 1100)])
+def test_structured_argmax_under_the_max_plus_scan_at_17_to_32_tags(crf, oracle_mod, T, N):
+    """Long chains: the structured argmax takes the max-plus scan where the dense one does (chunk products from the
+    transition entries in registers and the streamed emissions): the dense call's tags and scores bit for bit."""
+    B = 2
+    assert crf.auto_algo(crf.OP_ARGMAX, B, N, T) == crf.ALGO_SCAN
+    emit, trans = _make(7650 + T, B, N, T)
+    trans[0, 2] = trans[3, 1] = float("-inf")
+    lens = torch.tensor([N, N - 41], dtype=torch.int32)
+    phi = (emit[:, :, None, :] + trans[None, None]).contiguous().cuda()
+    s_a, y_a = crf.lccrf_argmax_structured(emit.cuda(), trans.cuda(), lens.cuda())
+    s_b, y_b = crf.lccrf_argmax(phi, lens.cuda(), algo=crf.ALGO_SEQUENTIAL)
+    assert torch.equal(y_a, y_b) and torch.equal(s_a, s_b)
+    _check(crf, oracle_mod, emit, trans, lens, f"structured max-plus scan T={T} N={N}")
+
+
 @pytest.mark.parametrize("T,N", [(9, 200), (16, 160), (24, 120), (40, 256)])
 def test_structured_scan_with_forbidden_transitions_and_peaked_emissions(crf, oracle_mod, T, N):
     """-inf transitions (the zero pattern of the chunk products) and emissions of scale 12 (the single-precision
