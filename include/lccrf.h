@@ -89,7 +89,7 @@ typedef enum {
     LCCRF_ALGO_SCAN = 2,       /* chunked associative scan over positions (the parallel variant the
                                   paper cites in "Sequence Tagging"): products of the T x T matrices
                                   of each chunk, a short serial pass over chunks, then every chunk
-                                  on its own.  T <= 32 for the sum queries, T <= 16 for lccrf_argmax, else
+                                  on its own.  T <= 64 for the sum queries, T <= 32 for lccrf_argmax, else
                                   LCCRF_ENOTIMPL;
                                   AUTO takes it for long chains in small batches */
     LCCRF_ALGO_SEQUENTIAL_EXACT = 3, /* sequential, and every log-sum-exp shifted by its own maximum:
