@@ -75,7 +75,7 @@ def test_random_shape_off_the_16_byte_grid(crf, oracle_mod, k, B, N, T, scale, d
     if T <= 64:
         algos.append(crf.ALGO_SCAN)
     for algo in algos:
-        q = ("logz", "mu", "vit") if algo != crf.ALGO_SCAN or T <= 16 else ("logz", "mu")
+        q = ("logz", "mu", "vit") if algo != crf.ALGO_SCAN or T <= 32 else ("logz", "mu")
         check_case(crf, oracle_mod, phi, lens if ragged else None, poison=(dtype == "f32"), algo=algo, what=f"{what} algo={algo}", queries=q)
     if T <= 64:
         q = ("logz", "mu", "vit") if 8 <= T <= 48 else ("vit",)
