@@ -67,6 +67,8 @@ WORKLOADS = {
     # Beyond the five configurations: the largest tag set the library serves (profiles, timing sweeps).
     "t256": Workload("t256", 8, 64, 256, 256, "f32", 256, 256, "iid", 1.0,
                      "largest tag set: 4.3 GB of potentials, matrices streamed in row batches"),
+    "long32": Workload("long32", 9, 8, 4096, 32, "f32", 4096, 4096, "iid", 1.0,
+                       "long chains over 32 tags in a small batch: every query under the chunked scan"),
 }
 
 
