@@ -959,6 +959,14 @@ __device__ __forceinline__ void maxplus_product(int first, int last, int T, doub
     for (int jj = 0; jj < EPL; ++jj) out[r * TP + EPL * q + jj] = (r < T && EPL * q + jj < T) ? M[jj] : ninf;
 }
 
+// The plain instruction: the running maxima are loop-carried, and fmax() quiets them once an iteration (a ninth of
+// the product's instructions) although no operand here is ever a NaN (sums of finite values and -inf).
+__device__ __forceinline__ double scan_max_raw(double a, double b) {
+    double r;
+    asm("v_max_f64 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b));
+    return r;
+}
+
 // The same product for 17 .. 32 tags (32 x 32 matrices, 1024 candidates a position and lane pair).  Lane (a = lane / 8,
 // b = lane % 8) owns the 4 x 4 block M[4a .. 4a+3][4b .. 4b+3]: for a source tag s it needs four entries of column s
 // of M and four of row s of X, 48 or 64 bytes of LDS for sixteen candidates (a lane that owned part of a row, as
@@ -1012,7 +1020,7 @@ __device__ __forceinline__ void maxplus_product32(int first, int last, int T, do
             for (int j = 0; j < 4; ++j) {
                 const double xj = (double)x[j];
 #pragma unroll
-                for (int i = 0; i < 4; ++i) best[i][j] = fmax(best[i][j], m[i] + xj);
+                for (int i = 0; i < 4; ++i) best[i][j] = scan_max_raw(best[i][j], m[i] + xj);
             }
         };
         double ma[4], mb[4];
